@@ -1,0 +1,388 @@
+"""The sumcheck instances of zkDL: product, matmul, Hadamard, zkReLU, aggregate.
+
+Each prover draws its points from the transcript, runs the textbook sumcheck of
+`oracle.sumcheck`, and returns proof bytes in the format the HIP library also
+emits (layout in the repository's design notes).  Each has a verifier that
+replays the transcript and checks the final claim against the reported finals.
+Test infrastructure; not used by the product.
+"""
+import struct
+
+import numpy as np
+
+from .field import R_MOD, fr_array, to_le, from_le
+from .mle import ilog2, beta_table, mle_eval, partial_eval
+from .sumcheck import SumcheckProof, prove, verify_rounds
+
+ZKRL_MAGIC = 0x4C524B5A   # bytes "ZKRL"
+ZKAG_MAGIC = 0x47414B5A   # bytes "ZKAG"
+
+
+def beta_point(u, v):
+    """beta~(u, v) for two field points: prod_k (u_k v_k + (1-u_k)(1-v_k))."""
+    assert len(u) == len(v)
+    acc = 1
+    for a, b in zip(u, v):
+        acc = acc * ((a * b + (1 - a) * (1 - b)) % R_MOD) % R_MOD
+    return acc
+
+
+def index_bits(index, nbits):
+    """Boolean point of an index, most significant bit first."""
+    return [(index >> (nbits - 1 - k)) & 1 for k in range(nbits)]
+
+
+# --------------------------------------------------------------------------
+# generic product of K tables (the micro-benchmark instance)
+# --------------------------------------------------------------------------
+def product_prove(tables, ts):
+    k = len(tables)
+    d = ilog2(len(tables[0]))
+    ts.absorb_u32(b"sumcheck_product", [k, d])
+    proof, vs = prove(tables, [(1, list(range(k)))], k, ts)
+    return proof.to_bytes(), proof, vs
+
+
+def product_verify(buf, k, d, ts):
+    proof, _ = SumcheckProof.from_bytes(buf)
+    assert proof.n_finals == k and proof.degree == k and len(proof.rounds) == d
+    ts.absorb_u32(b"sumcheck_product", [k, d])
+    claim, vs = verify_rounds(proof, ts)
+    prod = 1
+    for f in proof.finals:
+        prod = prod * f % R_MOD
+    assert prod == claim, "final claim != product of finals"
+    return proof, vs
+
+
+# --------------------------------------------------------------------------
+# batched matrix product (Eq. exm-matmul-batched)
+# --------------------------------------------------------------------------
+def matmul_prove(x0, shape0, x1, shape1, ts):
+    """Y[n] = X0[n] X1[n], X0 [N,D1,D2], X1 [N,D2,D3]: prove
+    Y~(w,u0,u1) = sum_{n,i} beta~(w,n) X0~(n,u0,i) X1~(n,i,u1).
+    Draws w, u0, u1 in that order.  Finals: beta~(w,v_n), X0~(v_n,u0,v_i),
+    X1~(v_n,v_i,u1)."""
+    n, d1, d2 = shape0
+    n_, d2_, d3 = shape1
+    assert n == n_ and d2 == d2_
+    ts.absorb_u32(b"sumcheck_matmul", [n, d1, d2, d3])
+    w = ts.challenges_vec(ilog2(n))
+    u0 = ts.challenges_vec(ilog2(d1))
+    u1 = ts.challenges_vec(ilog2(d3))
+    t0, _ = partial_eval(x0, [n, d1, d2], 1, 2, u0)          # [N, D2]
+    t1, _ = partial_eval(x1, [n, d2, d3], 2, 3, u1)          # [N, D2]
+    tb = np.repeat(beta_table(w), d2)                         # beta~(w,n), every i
+    proof, vs = prove([tb, t0, t1], [(1, [0, 1, 2])], 3, ts)
+    return proof.to_bytes(), proof, dict(w=w, u0=u0, u1=u1, v=vs)
+
+
+def matmul_verify(buf, n, d1, d2, d3, ts):
+    proof, _ = SumcheckProof.from_bytes(buf)
+    assert proof.n_finals == 3 and proof.degree == 3
+    assert len(proof.rounds) == ilog2(n) + ilog2(d2)
+    ts.absorb_u32(b"sumcheck_matmul", [n, d1, d2, d3])
+    w = ts.challenges_vec(ilog2(n))
+    u0 = ts.challenges_vec(ilog2(d1))
+    u1 = ts.challenges_vec(ilog2(d3))
+    claim, vs = verify_rounds(proof, ts)
+    fb, f0, f1 = proof.finals
+    assert fb == beta_point(w, vs[:len(w)]), "beta final is not beta~(w, v_n)"
+    assert fb * f0 % R_MOD * f1 % R_MOD == claim, "final claim mismatch"
+    return proof, dict(w=w, u0=u0, u1=u1, v=vs)
+
+
+# --------------------------------------------------------------------------
+# batched Hadamard product (Eq. exm-hadamard-batched)
+# --------------------------------------------------------------------------
+def hadamard_prove(x0, x1, ts):
+    """Y = X0 (.) X1 over the whole stack: Y~(p) = sum_b beta~(p,b) X0(b) X1(b);
+    p = (w, u) is drawn as one point over all variables."""
+    d = ilog2(len(x0))
+    assert len(x1) == len(x0)
+    ts.absorb_u32(b"sumcheck_hadamard", [d])
+    p = ts.challenges_vec(d)
+    proof, vs = prove([beta_table(p), x0, x1], [(1, [0, 1, 2])], 3, ts)
+    return proof.to_bytes(), proof, dict(p=p, v=vs)
+
+
+def hadamard_verify(buf, d, ts):
+    proof, _ = SumcheckProof.from_bytes(buf)
+    assert proof.n_finals == 3 and proof.degree == 3 and len(proof.rounds) == d
+    ts.absorb_u32(b"sumcheck_hadamard", [d])
+    p = ts.challenges_vec(d)
+    claim, vs = verify_rounds(proof, ts)
+    fb, f0, f1 = proof.finals
+    assert fb == beta_point(p, vs)
+    assert fb * f0 % R_MOD * f1 % R_MOD == claim
+    return proof, dict(p=p, v=vs)
+
+
+# --------------------------------------------------------------------------
+# zkReLU (Sec. 3.1, App. A)
+# --------------------------------------------------------------------------
+def recomposition_vectors(q, r_bits):
+    """s_{Q+R} and s' padded with zeros to the next power of two J.
+
+    s_B = (1, 2, ..., 2^{B-2}, -2^{B-1}) (Sec. 3.1).  s' picks out the rescaled
+    value: aux[R:Q+R] . s_Q + aux[R-1], i.e. (0^{R-1}, 1, 1, 2, ..., 2^{Q-2},
+    -2^{Q-1}) (App. A)."""
+    b = q + r_bits
+    j_pad = 1 << (b - 1).bit_length()
+    s = [0] * j_pad
+    sp = [0] * j_pad
+    for j in range(b - 1):
+        s[j] = 1 << j
+    s[b - 1] = -(1 << (b - 1))
+    sp[r_bits - 1] = 1
+    for j in range(r_bits, b - 1):
+        sp[j] = 1 << (j - r_bits)
+    sp[b - 1] = -(1 << (q - 1))
+    return s, sp, j_pad
+
+
+def aux_bits(values, nbits, j_pad):
+    """Two's-complement bits of (Q+R)-bit integers, zero-padded to j_pad columns
+    (Eqs. aux-Z, aux-GA).  Raises ValueError on a value outside the range the
+    completeness theorem assumes."""
+    lim = 1 << (nbits - 1)
+    out = np.zeros((len(values), j_pad), dtype=object)
+    for i, x in enumerate(values):
+        x = int(x)
+        if not (-lim <= x < lim):
+            raise ValueError(f"value {x} is not a {nbits}-bit signed integer")
+        for j in range(nbits):
+            out[i, j] = (x >> j) & 1
+    return out
+
+
+def zkrelu_witness(z, ga, q, r_bits):
+    """aux and every tensor recomposed from it (Sec. 3.1): Z, Z', sign, A,
+    G_A, G_A', G_Z as signed Python ints."""
+    s, sp, j_pad = recomposition_vectors(q, r_bits)
+    b = q + r_bits
+    aux0 = aux_bits(z, b, j_pad)
+    aux1 = aux_bits(ga, b, j_pad)
+    sv = np.array(s, dtype=object)
+    spv = np.array(sp, dtype=object)
+    z_rec = aux0.dot(sv)
+    ga_rec = aux1.dot(sv)
+    zp = aux0.dot(spv)
+    gap = aux1.dot(spv)
+    sgn = aux0[:, b - 1].copy()
+    a = (1 - sgn) * zp
+    gz = (1 - sgn) * gap
+    return dict(aux0=aux0, aux1=aux1, s=s, sp=sp, j_pad=j_pad, Z=z_rec, GA=ga_rec,
+                Zp=zp, GAp=gap, sgn=sgn, A=a, GZ=gz)
+
+
+def _merge_tables(m_table, wbar, rho, b, lj):
+    """E = rho0 beta~((0,wbar),.) + rho1 beta~((1,wbar),.) + rho2 beta~((0,e_{B-1}),.)"""
+    e_sign = index_bits(b - 1, lj)
+    e = (rho[0] * beta_table([0] + list(wbar))
+         + rho[1] * beta_table([1] + list(wbar))
+         + rho[2] * beta_table([0] + e_sign)) % R_MOD
+    return [np.asarray(m_table, dtype=object).reshape(-1), e]
+
+
+def zkrelu_prove(z, ga, q, r_bits, ts):
+    """Combined zkReLU sumcheck (App. A) followed by the merge of the three
+    claims on aux into one.
+
+    `ga=None` is the forward-only use: it stands for G_A = 0, for which the
+    three backward equations hold trivially.
+    Transcript order: header; u_Z, u_A, u_GA, u_GZ (log D each), u_bin
+    (log D + log J); absorb the four input claims; r, r'; rounds; finals
+    (aux~(0,v,wbar), aux~(1,v,wbar), aux~(0,v,Q+R-1)); rho0..2; merge rounds;
+    merge finals (aux~(k*,v,w*), E~(k*,w*))."""
+    d_len = len(z)
+    has_ga = ga is not None
+    if ga is None:
+        ga = [0] * d_len
+    assert len(ga) == d_len
+    wit = zkrelu_witness(z, ga, q, r_bits)
+    j_pad = wit["j_pad"]
+    li, lj = ilog2(d_len), ilog2(j_pad)
+    b = q + r_bits
+    ts.absorb_u32(b"zkrelu", [li, q, r_bits, 1 if has_ga else 0])
+    u_z = ts.challenges_vec(li)
+    u_a = ts.challenges_vec(li)
+    u_ga = ts.challenges_vec(li)
+    u_gz = ts.challenges_vec(li)
+    u_bin = ts.challenges_vec(li + lj)
+    c_in = [mle_eval(fr_array(wit["Z"]), u_z), mle_eval(fr_array(wit["A"]), u_a),
+            mle_eval(fr_array(wit["GA"]), u_ga), mle_eval(fr_array(wit["GZ"]), u_gz)]
+    ts.absorb_fr(b"c", c_in)
+    r = ts.challenge()
+    rp = ts.challenge()
+
+    def over_i(col):      # a table of D values, constant in j
+        return np.repeat(np.asarray(col, dtype=object), j_pad)
+
+    def over_j(row):      # a table of J values, constant in i
+        return np.tile(fr_array(row), d_len)
+
+    tables = [
+        over_i(beta_table(u_z)),            # 0  beta~(u_Z, i)
+        over_i(beta_table(u_a)),            # 1  beta~(u_A, i)
+        over_i(beta_table(u_ga)),           # 2  beta~(u_GA, i)
+        over_i(beta_table(u_gz)),           # 3  beta~(u_GZ, i)
+        beta_table(u_bin),                  # 4  beta~(u_bin, (i,j))
+        fr_array(wit["aux0"]),              # 5  aux(0,i,j)
+        fr_array(wit["aux1"]),              # 6  aux(1,i,j)
+        over_i(fr_array(1 - wit["sgn"])),   # 7  1 - aux(0,i,Q+R-1)
+        over_j(wit["s"]),                   # 8  s_{Q+R}(j)
+        over_j(wit["sp"]),                  # 9  s'(j)
+    ]
+    r2 = r * r % R_MOD
+    terms = [
+        (r2, [0, 5, 8]),                    # forward in   (weight r^2)
+        (r, [1, 7, 5, 9]),                  # forward out  (weight r)
+        (1, [4, 5, 5]), (R_MOD - 1, [4, 5]),            # forward binarity (weight 1)
+        (rp * r2 % R_MOD, [2, 6, 8]),       # backward in  (weight r' r^2)
+        (rp * r % R_MOD, [3, 7, 6, 9]),     # backward out (weight r' r)
+        (rp, [4, 6, 6]), (R_MOD - rp, [4, 6]),          # backward binarity (weight r')
+    ]
+    proof, vs = prove(tables, terms, 3, ts, absorb_claim=False,
+                      report=lambda f: [f[5], f[6], 1 - f[7]])
+    expect0 = (r2 * c_in[0] + r * c_in[1] + rp * r2 * c_in[2] + rp * r * c_in[3]) % R_MOD
+    assert proof.claim0 == expect0, "combined claim is not the weighted sum of the input claims"
+    v_i, wbar = vs[:li], vs[li:]
+
+    # merge: M[k, j] = aux~(k, v, j)
+    aux = np.concatenate([fr_array(wit["aux0"]), fr_array(wit["aux1"])])
+    m_table, _ = partial_eval(aux, [2, d_len, j_pad], 1, 2, v_i)
+    assert mle_eval(m_table[:j_pad], wbar) == proof.finals[0]
+    assert mle_eval(m_table[j_pad:], wbar) == proof.finals[1]
+    assert m_table[b - 1] == proof.finals[2]
+    rho = ts.challenges_vec(3)
+    merge, vm = prove(_merge_tables(m_table, wbar, rho, b, lj), [(1, [0, 1])], 2, ts,
+                      absorb_claim=False)
+    assert merge.claim0 == sum(x * y for x, y in zip(rho, proof.finals)) % R_MOD
+
+    head = struct.pack("<IIIIIIII", ZKRL_MAGIC, li, q, r_bits, 1 if has_ga else 0, 0, 0, 0)
+    buf = head + b"".join(to_le(c) for c in c_in) + proof.to_bytes() + merge.to_bytes()
+    info = dict(u_z=u_z, u_a=u_a, u_ga=u_ga, u_gz=u_gz, u_bin=u_bin, c_in=c_in, r=r, rp=rp,
+                v=vs, rho=rho, vm=vm, proof=proof, merge=merge, wit=wit)
+    return buf, info
+
+
+def zkrelu_verify(buf, ts, off=0):
+    """Replay a zkReLU proof.  Checks every round, the final combined claim and
+    the merge; the one remaining claim on aux, (k*, v, w*) -> value, is returned
+    for the (out-of-scope) proof of evaluation."""
+    magic, li, q, r_bits, has_ga, _, _, _ = struct.unpack_from("<IIIIIIII", buf, off)
+    assert magic == ZKRL_MAGIC
+    off += 32
+    c_in = [from_le(buf[off + 32 * k: off + 32 * k + 32]) for k in range(4)]
+    off += 128
+    proof, off = SumcheckProof.from_bytes(buf, off)
+    merge, off = SumcheckProof.from_bytes(buf, off)
+    s, sp, j_pad = recomposition_vectors(q, r_bits)
+    lj = ilog2(j_pad)
+    b = q + r_bits
+    assert proof.degree == 3 and len(proof.rounds) == li + lj and proof.n_finals == 3
+    assert merge.degree == 2 and len(merge.rounds) == 1 + lj and merge.n_finals == 2
+    ts.absorb_u32(b"zkrelu", [li, q, r_bits, has_ga])
+    u_z = ts.challenges_vec(li)
+    u_a = ts.challenges_vec(li)
+    u_ga = ts.challenges_vec(li)
+    u_gz = ts.challenges_vec(li)
+    u_bin = ts.challenges_vec(li + lj)
+    ts.absorb_fr(b"c", c_in)
+    r = ts.challenge()
+    rp = ts.challenge()
+    r2 = r * r % R_MOD
+    expect0 = (r2 * c_in[0] + r * c_in[1] + rp * r2 * c_in[2] + rp * r * c_in[3]) % R_MOD
+    claim, vs = verify_rounds(proof, ts, absorb_claim=False, expected_claim0=expect0)
+    v_i, wbar = vs[:li], vs[li:]
+    a0, a1, sg = proof.finals
+    s_w = mle_eval(fr_array(s), wbar)
+    sp_w = mle_eval(fr_array(sp), wbar)
+    b_bin = beta_point(u_bin, vs)
+    rhs = (r2 * beta_point(u_z, v_i) % R_MOD * a0 % R_MOD * s_w
+           + r * beta_point(u_a, v_i) % R_MOD * (1 - sg) % R_MOD * a0 % R_MOD * sp_w
+           + b_bin * (a0 * a0 - a0)
+           + rp * (r2 * beta_point(u_ga, v_i) % R_MOD * a1 % R_MOD * s_w
+                   + r * beta_point(u_gz, v_i) % R_MOD * (1 - sg) % R_MOD * a1 % R_MOD * sp_w
+                   + b_bin * (a1 * a1 - a1))) % R_MOD
+    assert rhs == claim, "zkReLU final claim mismatch"
+    rho = ts.challenges_vec(3)
+    expect_m = (rho[0] * a0 + rho[1] * a1 + rho[2] * sg) % R_MOD
+    claim_m, vm = verify_rounds(merge, ts, absorb_claim=False, expected_claim0=expect_m)
+    m_f, e_f = merge.finals
+    e_pub = (rho[0] * beta_point([0] + wbar, vm) + rho[1] * beta_point([1] + wbar, vm)
+             + rho[2] * beta_point([0] + index_bits(b - 1, lj), vm)) % R_MOD
+    assert e_f == e_pub, "E final is not the public combination of beta values"
+    assert m_f * e_f % R_MOD == claim_m, "merge final claim mismatch"
+    aux_claim = dict(point=[vm[0]] + v_i + vm[1:], value=m_f)
+    return off, dict(c_in=c_in, points=dict(u_z=u_z, u_a=u_a, u_ga=u_ga, u_gz=u_gz),
+                     aux_claim=aux_claim, v=vs, vm=vm)
+
+
+# --------------------------------------------------------------------------
+# aggregated proof of one window of training steps (Sec. 5, Example FCNN)
+# --------------------------------------------------------------------------
+def shift_layers(stack, n_layers):
+    """Slot (t, l) <- slot (t, l+1); the last layer's slot of every step is zero.
+    `stack` has the stack axis first."""
+    stack = np.asarray(stack)
+    out = np.zeros_like(stack)
+    n = stack.shape[0]
+    for k in range(n):
+        if k % n_layers != n_layers - 1:
+            out[k] = stack[k + 1]
+    return out
+
+
+def aggregate_prove(wit, ts):
+    """One proof for a window of T' steps of an L-layer FCNN (Protocol zkdl,
+    the sumcheck line only).  Families, in order: forward Z = A W; gradA
+    G_A = G_Z^{(l+1)} W^{(l+1)T}; gradW G_W = A^T G_Z; zkReLU on the stacked Z, G_A.
+    `wit`: dict with L, B, width, T, Q, R and integer stacks A [N,B,w], W [N,w,w],
+    GZ [N,B,w], Zr [N,B,w], GA [N,B,w], N = T L, slot n = t L + (l-1)."""
+    n_layers, bsz, width, steps = wit["L"], wit["B"], wit["width"], wit["T"]
+    q, r_bits = wit["Q"], wit["R"]
+    n = n_layers * steps
+    a = np.asarray(wit["A"]).reshape(n, bsz, width)
+    w = np.asarray(wit["W"]).reshape(n, width, width)
+    gz = np.asarray(wit["GZ"]).reshape(n, bsz, width)
+    ts.absorb_u32(b"aggregate", [n_layers, bsz, width, steps, q, r_bits])
+    parts = [struct.pack("<IIIIIIII", ZKAG_MAGIC, n_layers, bsz, width, steps, q, r_bits, 0)]
+    infos = {}
+    # forward: X0 = A [N,B,w], X1 = W [N,w,w]
+    buf, _, infos["fwd"] = matmul_prove(fr_array(a), [n, bsz, width], fr_array(w),
+                                        [n, width, width], ts)
+    parts.append(buf)
+    # gradA: X0 = G_Z of the next layer [N,B,w], X1 = W of the next layer, transposed
+    gz_next = shift_layers(gz, n_layers)
+    wt_next = np.transpose(shift_layers(w, n_layers), (0, 2, 1))
+    buf, _, infos["gradA"] = matmul_prove(fr_array(gz_next), [n, bsz, width], fr_array(wt_next),
+                                          [n, width, width], ts)
+    parts.append(buf)
+    # gradW: X0 = A^T [N,w,B], X1 = G_Z [N,B,w]
+    a_t = np.transpose(a, (0, 2, 1))
+    buf, _, infos["gradW"] = matmul_prove(fr_array(a_t), [n, width, bsz], fr_array(gz),
+                                          [n, bsz, width], ts)
+    parts.append(buf)
+    buf, infos["zkrelu"] = zkrelu_prove(np.asarray(wit["Zr"]).reshape(-1).tolist(),
+                                        np.asarray(wit["GA"]).reshape(-1).tolist(), q, r_bits, ts)
+    parts.append(buf)
+    return b"".join(parts), infos
+
+
+def aggregate_verify(buf, ts):
+    magic, n_layers, bsz, width, steps, q, r_bits, _ = struct.unpack_from("<IIIIIIII", buf, 0)
+    assert magic == ZKAG_MAGIC
+    n = n_layers * steps
+    ts.absorb_u32(b"aggregate", [n_layers, bsz, width, steps, q, r_bits])
+    off = 32
+    out = {}
+    for name, (d1, d2, d3) in (("fwd", (bsz, width, width)), ("gradA", (bsz, width, width)),
+                               ("gradW", (width, bsz, width))):
+        proof, end = SumcheckProof.from_bytes(buf, off)
+        out[name] = matmul_verify(buf[off:end], n, d1, d2, d3, ts)
+        off = end
+    off, out["zkrelu"] = zkrelu_verify(buf, ts, off)
+    assert off == len(buf)
+    return out

@@ -1,0 +1,121 @@
+"""Pins for the oracle's sumcheck prover and the matmul / Hadamard instances."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle.field import R_MOD, fr_array, to_le
+from oracle.mle import mle_eval, beta_table
+from oracle.sumcheck import lagrange_eval, prove, SumcheckProof
+from oracle import protocols as P
+from oracle.transcript import Transcript
+
+rng = np.random.default_rng(23)
+
+
+def rand_fr(n):
+    return [int.from_bytes(rng.bytes(40), "little") % R_MOD for _ in range(n)]
+
+
+def test_lagrange_on_known_polynomials():
+    # x^3 through its values at 0..3 ; 2x^2 - 3x + 5 through 0..2
+    assert lagrange_eval([0, 1, 8, 27], 5) == 125
+    assert lagrange_eval([0, 1, 8, 27], R_MOD - 2) == (-8) % R_MOD
+    assert lagrange_eval([5, 4, 7], 10) == 175
+    ys = rand_fr(4)
+    for k in range(4):
+        assert lagrange_eval(ys, k) == ys[k]
+
+
+@pytest.mark.parametrize("k,d", [(1, 3), (2, 4), (3, 5), (3, 1)])
+def test_product_sumcheck_against_brute_force(k, d):
+    tabs = [fr_array(rand_fr(1 << d)) for _ in range(k)]
+    ts = Transcript(3)
+    buf, proof, vs = P.product_prove(tabs, ts)
+    # claim_0 is the sum over the Boolean hypercube, written as a plain loop
+    brute = 0
+    for b in range(1 << d):
+        term = 1
+        for t in tabs:
+            term = term * t[b] % R_MOD
+        brute = (brute + term) % R_MOD
+    assert proof.claim0 == brute
+    # every round polynomial equals the definition: bind the past challenges, set
+    # the current variable to x, sum the rest over Boolean values
+    for t, g in enumerate(proof.rounds):
+        for x in range(k + 1):
+            acc = 0
+            for rest in itertools.product((0, 1), repeat=d - t - 1):
+                pt = vs[:t] + [x] + list(rest)
+                term = 1
+                for tab in tabs:
+                    term = term * mle_eval(tab, pt) % R_MOD
+                acc = (acc + term) % R_MOD
+            assert g[x] == acc
+    # finals are the evaluations of the original tables at the challenge point
+    assert proof.finals == [mle_eval(t, vs) for t in tabs]
+    # bytes round-trip and the verifier accepts, ending in the same transcript state
+    assert SumcheckProof.from_bytes(buf)[0].to_bytes() == buf
+    assert len(buf) == 16 + 32 * (1 + d * (k + 1) + k)
+    tv = Transcript(3)
+    P.product_verify(buf, k, d, tv)
+    assert tv.digest() == ts.digest() and tv.challenges == ts.challenges
+
+
+def test_product_verifier_rejects_any_tampered_element():
+    tabs = [fr_array(rand_fr(8)) for _ in range(3)]
+    buf, _, _ = P.product_prove(tabs, Transcript(1))
+    n_el = (len(buf) - 16) // 32
+    for e in range(n_el):
+        bad = bytearray(buf)
+        bad[16 + 32 * e] ^= 1
+        with pytest.raises(AssertionError):
+            P.product_verify(bytes(bad), 3, 3, Transcript(1))
+
+
+def test_prover_asserts_on_inconsistent_tables():
+    # a planted mistake in the oracle's own fold must trip its round invariant:
+    # here the "table" is changed between claim and rounds by a wrong term list
+    tabs = [fr_array(rand_fr(8)) for _ in range(2)]
+    ts = Transcript(1)
+    good, _ = prove(tabs, [(1, [0, 1])], 2, ts)
+    ts = Transcript(1)
+    with pytest.raises(AssertionError):
+        prove(tabs, [(1, [0, 1])], 1, ts)      # degree too low: g(v) != next sum
+
+
+@pytest.mark.parametrize("n,d1,d2,d3", [(1, 4, 8, 2), (4, 2, 4, 8), (2, 1, 2, 1)])
+def test_matmul_claim_is_mle_of_integer_matmul(n, d1, d2, d3):
+    x0 = rng.integers(-2 ** 31, 2 ** 31, (n, d1, d2))
+    x1 = rng.integers(-2 ** 31, 2 ** 31, (n, d2, d3))
+    y = np.einsum("nij,njk->nik", x0.astype(object), x1.astype(object))   # exact integers
+    ts = Transcript(4)
+    buf, proof, pts = P.matmul_prove(fr_array(x0), [n, d1, d2], fr_array(x1), [n, d2, d3], ts)
+    assert proof.claim0 == mle_eval(fr_array(y), pts["w"] + pts["u0"] + pts["u1"])
+    ln = len(pts["w"])
+    vn, vi = pts["v"][:ln], pts["v"][ln:]
+    assert proof.finals[0] == mle_eval(beta_table(pts["w"]), vn)
+    assert proof.finals[1] == mle_eval(fr_array(x0), vn + pts["u0"] + vi)
+    assert proof.finals[2] == mle_eval(fr_array(x1), vn + vi + pts["u1"])
+    tv = Transcript(4)
+    P.matmul_verify(buf, n, d1, d2, d3, tv)
+    assert tv.digest() == ts.digest()
+    bad = bytearray(buf)
+    bad[16 + 32 * 3] ^= 1
+    with pytest.raises(AssertionError):
+        P.matmul_verify(bytes(bad), n, d1, d2, d3, Transcript(4))
+
+
+def test_hadamard_claim_is_mle_of_integer_product():
+    shape = (2, 4, 4)
+    x0 = rng.integers(-2 ** 31, 2 ** 31, shape)
+    x1 = rng.integers(-2 ** 31, 2 ** 31, shape)
+    y = x0.astype(object) * x1.astype(object)
+    ts = Transcript(6)
+    buf, proof, pts = P.hadamard_prove(fr_array(x0), fr_array(x1), ts)
+    assert proof.claim0 == mle_eval(fr_array(y), pts["p"])
+    assert proof.finals[1] == mle_eval(fr_array(x0), pts["v"])
+    assert proof.finals[2] == mle_eval(fr_array(x1), pts["v"])
+    tv = Transcript(6)
+    P.hadamard_verify(buf, 5, tv)
+    assert tv.digest() == ts.digest()
