@@ -1,0 +1,190 @@
+/* zkdl.h - C ABI of the MI355X tensor-sumcheck prover for zkDL (arXiv 2307.16273).
+ *
+ * The library proves, on one gfx950 GPU, the sumcheck instances that zkDL uses
+ * for a training step over the BLS12-381 scalar field Fr: multilinear-extension
+ * partial evaluations (Sec. 2.2, Eq. multilinear-extension), batched matrix and
+ * Hadamard products (Sec. 4, Eqs. exm-matmul-batched, exm-hadamard-batched),
+ * zkReLU (Sec. 3.1, App. A) and their aggregation over layers and steps (Sec. 5,
+ * Protocol zkdl, the sumcheck line).  The verifier's random messages of the
+ * interactive protocols (App. B) are replaced by a SHA-256 Fiat-Shamir
+ * transcript that runs on the device next to the kernels.
+ *
+ * Conventions
+ *  - Every function returns ZKDL_OK (0) or a negative zkdl_err; nothing aborts
+ *    or throws.  After ZKDL_EHIP, zkdl_last_hip_error() gives the HIP code.
+ *  - "host" / "device" is stated for every pointer.  The caller owns every
+ *    buffer it passes; the library owns zkdl_tensor storage and its scratch.
+ *  - Field elements cross the boundary as zkdl_fr: 32 bytes, canonical (fully
+ *    reduced), little-endian, NOT in Montgomery form.
+ *  - Tensors are row-major, every dimension a power of two (pad with zeros
+ *    otherwise, Sec. 2.2).  A point is the concatenation of one vector per
+ *    axis, leading axis first; inside an axis coordinate 0 pairs with the most
+ *    significant bit of that axis' index.
+ *  - A call enqueues its kernels on the context's stream and returns after the
+ *    proof bytes have been copied to the caller's host buffer (it synchronises
+ *    that stream once, at the end).  Calls on one context must not overlap.
+ *  - points_out / npoints: if points_out != NULL, *npoints holds its capacity
+ *    on entry; on return the challenges drawn during the call are stored in
+ *    draw order and *npoints is their number (ZKDL_ESMALL if too small).
+ *  - proof / proof_len: *proof_len holds the capacity in bytes on entry and the
+ *    bytes written on return.  ZKDL_ESMALL sets *proof_len to the size needed.
+ *
+ * Proof layout (all integers little-endian u32, all field elements zkdl_fr)
+ *   SC block : "ZKSC", n_finals, degree, rounds, claim_0,
+ *              rounds x (degree+1) evaluations g_t(0..degree), n_finals finals
+ *   zkReLU   : "ZKRL", log2 D, Q, R, has_ga, 0, 0, 0, four input claims
+ *              (Z, A, G_A, G_Z), SC block (degree 3, finals aux~(0,v,w),
+ *              aux~(1,v,w), aux~(0,v,Q+R-1)), SC block of the merge (degree 2,
+ *              finals aux~(k*,v,w*), E~(k*,w*))
+ *   aggregate: "ZKAG", L, B, width, T', Q, R, 0, SC block forward, SC block
+ *              gradA, SC block gradW, zkReLU proof
+ */
+#ifndef ZKDL_H
+#define ZKDL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZKDL_OK = 0,
+    ZKDL_EINVAL = -1, /* null pointer, bad dtype, dimension not a power of two, shape mismatch */
+    ZKDL_ERANGE = -2, /* a zkReLU input is not a (Q+R)-bit signed integer (Theorem completeness) */
+    ZKDL_ENOMEM = -3, /* device or host allocation failed */
+    ZKDL_EHIP = -4,   /* a HIP runtime call failed */
+    ZKDL_ESMALL = -5  /* an output buffer is too small */
+} zkdl_err;
+
+typedef enum { ZKDL_I32 = 0, ZKDL_I64 = 1, ZKDL_FR_LE = 2 } zkdl_dtype;
+
+typedef struct zkdl_ctx zkdl_ctx;               /* device id + borrowed hipStream_t + scratch */
+typedef struct zkdl_tensor zkdl_tensor;         /* device tensor: Fr (SoA limb planes, Montgomery) or borrowed integers */
+typedef struct zkdl_transcript zkdl_transcript; /* SHA-256 Fiat-Shamir state, host side */
+typedef struct { uint8_t le[32]; } zkdl_fr;
+
+#define ZKDL_MAX_DIMS 4
+
+/* ---- context ------------------------------------------------------------ */
+/* hip_stream: a hipStream_t (e.g. torch.cuda.current_stream().cuda_stream), or
+ * NULL for the default stream.  The stream is borrowed, never destroyed. */
+int zkdl_ctx_create(zkdl_ctx** out, int device, void* hip_stream);
+int zkdl_ctx_destroy(zkdl_ctx* ctx);
+int zkdl_last_hip_error(const zkdl_ctx* ctx);
+const char* zkdl_strerror(int err);
+/* Frees cached scratch memory (the context keeps freed blocks for reuse). */
+int zkdl_ctx_trim(zkdl_ctx* ctx);
+
+/* ---- transcript (host side; format in the header comment of this file) --- */
+int zkdl_transcript_create(zkdl_transcript** out, uint64_t seed);
+int zkdl_transcript_destroy(zkdl_transcript* t);
+int zkdl_transcript_absorb(zkdl_transcript* t, const char* label, const void* host_bytes, size_t n);
+int zkdl_transcript_challenge(zkdl_transcript* t, zkdl_fr* host_out);
+int zkdl_transcript_digest(const zkdl_transcript* t, uint8_t host_out[32]);
+
+/* ---- tensors --------------------------------------------------------------
+ * fr_tensor_upload: the discretised tensor of Sec. 2.2 mapped into Fr.  src is
+ * `numel` items of dtype (ZKDL_I32 / ZKDL_I64: signed, x -> x mod r;
+ * ZKDL_FR_LE: 32-byte little-endian values, reduced mod r), in host memory or,
+ * if src_on_device != 0, in device memory.  The result is Fr in Montgomery
+ * form, eight 32-bit limb planes (structure of arrays). */
+int fr_tensor_upload(zkdl_ctx* ctx, const void* src, int dtype, int src_on_device,
+                     const uint64_t* shape, int ndim, zkdl_tensor** out);
+/* A view of integers already in device memory (no copy, memory stays the
+ * caller's and must outlive the tensor).  Accepted wherever a tensor is read;
+ * the conversion into Fr happens inside the consuming kernel. */
+int zkdl_tensor_wrap_int(zkdl_ctx* ctx, const void* device_src, int dtype, const uint64_t* shape,
+                         int ndim, zkdl_tensor** out);
+int zkdl_tensor_ndim(const zkdl_tensor* t);
+uint64_t zkdl_tensor_dim(const zkdl_tensor* t, int axis);
+uint64_t zkdl_tensor_numel(const zkdl_tensor* t);
+/* Canonical bytes of every element, row-major, into host memory (numel x 32 B). */
+int zkdl_tensor_download(zkdl_ctx* ctx, const zkdl_tensor* t, zkdl_fr* host_out);
+int zkdl_tensor_free(zkdl_ctx* ctx, zkdl_tensor* t);
+
+/* ---- MLE partial evaluation (Eq. multilinear-extension, Sec. 2.2) ----------
+ * Binds the variables of axes [axis_lo, axis_hi) to `point` (host, npoint =
+ * sum of log2 of those dimensions):
+ *   out[o, i] = sum_a beta~(point, a) * t[o, a, i].
+ * The result has the remaining axes (ndim 0 = a single element). */
+int mle_partial_eval(zkdl_ctx* ctx, const zkdl_tensor* t, int axis_lo, int axis_hi,
+                     const zkdl_fr* point, size_t npoint, zkdl_tensor** out);
+
+/* ---- sumchecks -------------------------------------------------------------
+ * sumcheck_product: sum over the hypercube of the product of K (1..3) Fr
+ * tensors of equal numel 2^d, degree-K round polynomials (Sec. 2.2).  The
+ * inputs are not modified.  finals (host, K elements, may be NULL): the tables'
+ * evaluations at the challenge point.  Transcript: header, claim_0, then per
+ * round g_t(0..K) and one challenge, then the finals.  Proof: one SC block. */
+int sumcheck_product(zkdl_ctx* ctx, const zkdl_tensor* const* tables, int K, zkdl_transcript* tr,
+                     uint8_t* proof, size_t* proof_len, zkdl_fr* finals, zkdl_fr* points_out,
+                     size_t* npoints);
+
+/* sumcheck_matmul: Eq. exm-matmul-batched,
+ *   Y~(w,u0,u1) = sum_n sum_i beta~(w,n) X0~(n,u0,i) X1~(n,i,u1)
+ * for Y[n] = op(X0[n]) op(X1[n]).  X0, X1 are 3-d tensors with the stack axis
+ * first; transpose_xk != 0 means op() transposes the stored matrices (the
+ * kernel binds the other axis; nothing is copied).  Logical shapes
+ * op(X0[n]) [D1,D2], op(X1[n]) [D2,D3].  Draws w (log N), u0 (log D1),
+ * u1 (log D3), then one challenge per round (n variables first, then i).
+ * claims (host, 3 elements, may be NULL): Y~(w,u0,u1), X0~(v_n,u0,v_i),
+ * X1~(v_n,v_i,u1).  Proof: one SC block with K = 3 (beta~(w,.) is a table). */
+int sumcheck_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1, int transpose_x0,
+                    int transpose_x1, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+                    zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints);
+
+/* sumcheck_hadamard: Eq. exm-hadamard-batched over the whole stack,
+ *   Y~(p) = sum_b beta~(p,b) X0(b) X1(b),  p drawn over all log2(numel) variables.
+ * claims (host, 3, may be NULL): Y~(p), X0~(v), X1~(v). */
+int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1,
+                      zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
+                      zkdl_fr* points_out, size_t* npoints);
+
+/* zkrelu_prove: the combined sumcheck of App. A over aux in {0,1}^{2 x D x (Q+R)}
+ * (bit axis padded to a power of two), weights r^2, r, 1, r'r^2, r'r, r', then the
+ * merge of the three claims on aux into one.  Z, GA: D signed (Q+R)-bit
+ * integers each (host, or device if src_on_device != 0); GA == NULL is the
+ * forward-only use and stands for G_A = 0.  D a power of two, Q + R <= 64,
+ * R >= 1.  ZKDL_ERANGE if a value is out of range (the proof is then not
+ * produced).  claims (host, 4, may be NULL): Z~(u_Z), A~(u_A), G_A~(u_GA),
+ * G_Z~(u_GZ).  Draw order: u_Z, u_A, u_GA, u_GZ, u_bin, r, r', rounds, rho0..2,
+ * merge rounds. */
+int zkrelu_prove(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint64_t D, int Q, int R,
+                 int src_on_device, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+                 zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints);
+
+/* One aggregation window of an L-layer width x width FCNN (Example FCNN,
+ * Protocol zkdl): T' steps, stack slot n = t L + (l-1), N = T' L.  All five
+ * stacks are device memory, row-major:
+ *   A  int32 [N,B,width]      input of layer l
+ *   W  int32 [N,width,width]  weights of layer l at step t
+ *   GZ int32 [N,B,width]      gradient of Z^(l)
+ *   Zr int64 [N,B,width]      Z^(l) where a ReLU follows, zero in last-layer slots
+ *   GA int64 [N,B,width]      unscaled gradient of A^(l), zero in last-layer slots */
+typedef struct {
+    uint32_t L, B, width, T, Q, R;
+    const int32_t* A;
+    const int32_t* W;
+    const int32_t* GZ;
+    const int64_t* Zr;
+    const int64_t* GA;
+} zkdl_fcnn_witness;
+
+/* aggregate_prove: forward (Z = A W), gradA (G_A = G_Z^(l+1) W^(l+1)T, last
+ * slot of each step zero), gradW (G_W = A^T G_Z) matmul sumchecks and zkReLU on
+ * (Zr, GA), in that order on one transcript. */
+int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
+                    size_t* proof_len, zkdl_fr* points_out, size_t* npoints);
+
+/* ---- host-side self checks (no GPU needed) -------------------------------- */
+/* out = a * b mod r computed by the library's Montgomery code on the host. */
+int zkdl_host_fr_mul(const zkdl_fr* a, const zkdl_fr* b, zkdl_fr* out);
+/* Re-derives the Montgomery constants by modular doubling; ZKDL_OK if they match. */
+int zkdl_selfcheck_constants(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZKDL_H */

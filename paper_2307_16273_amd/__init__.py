@@ -1,0 +1,17 @@
+"""MI355X tensor-sumcheck prover for zkDL (arXiv 2307.16273): Python binding.
+
+A thin ctypes layer over the C ABI of libzkdl.so (include/zkdl.h), with the same
+entry-point names.  It only marshals arguments: every step of a proof runs in
+the library's HIP kernels.  PyTorch is used for device memory and the stream.
+There is no CPU fallback: if the library is missing, importing the binding's
+functions raises.
+"""
+from .binding import (Context, Transcript, FrTensor, ZkdlError, load_library, library_path,
+                      fr_tensor_upload, tensor_wrap_int, mle_partial_eval, sumcheck_product,
+                      sumcheck_matmul, sumcheck_hadamard, zkrelu_prove, aggregate_prove,
+                      host_fr_mul, selfcheck_constants, EXPORTED_SYMBOLS)
+
+__all__ = ["Context", "Transcript", "FrTensor", "ZkdlError", "load_library", "library_path",
+           "fr_tensor_upload", "tensor_wrap_int", "mle_partial_eval", "sumcheck_product",
+           "sumcheck_matmul", "sumcheck_hadamard", "zkrelu_prove", "aggregate_prove",
+           "host_fr_mul", "selfcheck_constants", "EXPORTED_SYMBOLS"]

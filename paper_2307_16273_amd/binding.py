@@ -1,0 +1,335 @@
+"""ctypes binding of libzkdl.so; argument marshalling only."""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+ZKDL_I32, ZKDL_I64, ZKDL_FR_LE = 0, 1, 2
+ERRORS = {0: "ok", -1: "ZKDL_EINVAL", -2: "ZKDL_ERANGE", -3: "ZKDL_ENOMEM", -4: "ZKDL_EHIP",
+          -5: "ZKDL_ESMALL"}
+
+EXPORTED_SYMBOLS = [
+    "zkdl_ctx_create", "zkdl_ctx_destroy", "zkdl_last_hip_error", "zkdl_strerror", "zkdl_ctx_trim",
+    "zkdl_transcript_create", "zkdl_transcript_destroy", "zkdl_transcript_absorb",
+    "zkdl_transcript_challenge", "zkdl_transcript_digest",
+    "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
+    "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
+    "mle_partial_eval", "sumcheck_product", "sumcheck_matmul", "sumcheck_hadamard",
+    "zkrelu_prove", "aggregate_prove", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
+]
+
+
+class ZkdlError(RuntimeError):
+    def __init__(self, code, where, hip=0):
+        self.code = code
+        self.hip = hip
+        super().__init__(f"{where}: {ERRORS.get(code, code)}" + (f" (hip error {hip})" if hip else ""))
+
+
+class FcnnWitness(C.Structure):
+    _fields_ = [("L", C.c_uint32), ("B", C.c_uint32), ("width", C.c_uint32), ("T", C.c_uint32),
+                ("Q", C.c_uint32), ("R", C.c_uint32),
+                ("A", C.c_void_p), ("W", C.c_void_p), ("GZ", C.c_void_p), ("Zr", C.c_void_p),
+                ("GA", C.c_void_p)]
+
+
+def library_path():
+    return os.path.join(_HERE, "libzkdl.so")
+
+
+def load_library():
+    """Loads libzkdl.so; raises if it has not been built (there is no fallback)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "or `python paper_2307_16273_amd/build.py`")
+    lib = C.CDLL(path)
+    vp, i, u64, sz = C.c_void_p, C.c_int, C.c_uint64, C.c_size_t
+    pp = C.POINTER(vp)
+    psz = C.POINTER(sz)
+    sig = {
+        "zkdl_ctx_create": [pp, i, vp], "zkdl_ctx_destroy": [vp], "zkdl_last_hip_error": [vp],
+        "zkdl_ctx_trim": [vp],
+        "zkdl_transcript_create": [pp, u64], "zkdl_transcript_destroy": [vp],
+        "zkdl_transcript_absorb": [vp, C.c_char_p, vp, sz], "zkdl_transcript_challenge": [vp, vp],
+        "zkdl_transcript_digest": [vp, vp],
+        "fr_tensor_upload": [vp, vp, i, i, C.POINTER(u64), i, pp],
+        "zkdl_tensor_wrap_int": [vp, vp, i, C.POINTER(u64), i, pp],
+        "zkdl_tensor_ndim": [vp], "zkdl_tensor_download": [vp, vp, vp], "zkdl_tensor_free": [vp, vp],
+        "mle_partial_eval": [vp, vp, i, i, vp, sz, pp],
+        "sumcheck_product": [vp, pp, i, vp, vp, psz, vp, vp, psz],
+        "sumcheck_matmul": [vp, vp, vp, i, i, vp, vp, psz, vp, vp, psz],
+        "sumcheck_hadamard": [vp, vp, vp, vp, vp, psz, vp, vp, psz],
+        "zkrelu_prove": [vp, vp, vp, u64, i, i, i, vp, vp, psz, vp, vp, psz],
+        "aggregate_prove": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
+        "zkdl_host_fr_mul": [vp, vp, vp], "zkdl_selfcheck_constants": [],
+    }
+    for name, args in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = i
+    lib.zkdl_strerror.argtypes = [i]
+    lib.zkdl_strerror.restype = C.c_char_p
+    lib.zkdl_tensor_dim.argtypes = [vp, i]
+    lib.zkdl_tensor_dim.restype = u64
+    lib.zkdl_tensor_numel.argtypes = [vp]
+    lib.zkdl_tensor_numel.restype = u64
+    _LIB = lib
+    return lib
+
+
+def _check(rc, where, ctx=None):
+    if rc != 0:
+        hip = load_library().zkdl_last_hip_error(ctx.handle) if (ctx is not None and rc == -4) else 0
+        raise ZkdlError(rc, where, hip)
+
+
+PROOF_CAP = 1 << 17
+POINTS_CAP = 1024
+
+
+class Context:
+    """Device context on the current PyTorch stream of `device`."""
+
+    def __init__(self, device=0, stream=None):
+        import torch
+        lib = load_library()
+        if stream is None:
+            stream = torch.cuda.current_stream(device).cuda_stream
+        self.handle = C.c_void_p()
+        self.device = device
+        _check(lib.zkdl_ctx_create(C.byref(self.handle), device, C.c_void_p(stream)), "zkdl_ctx_create")
+
+    def trim(self):
+        _check(load_library().zkdl_ctx_trim(self.handle), "zkdl_ctx_trim", self)
+
+    def close(self):
+        if self.handle:
+            load_library().zkdl_ctx_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Transcript:
+    def __init__(self, seed=0):
+        self.handle = C.c_void_p()
+        _check(load_library().zkdl_transcript_create(C.byref(self.handle), seed), "zkdl_transcript_create")
+
+    def absorb(self, label, data):
+        data = bytes(data)
+        buf = C.create_string_buffer(data, len(data))
+        _check(load_library().zkdl_transcript_absorb(self.handle, bytes(label), buf, len(data)),
+               "zkdl_transcript_absorb")
+
+    def challenge(self):
+        out = C.create_string_buffer(32)
+        _check(load_library().zkdl_transcript_challenge(self.handle, out), "zkdl_transcript_challenge")
+        return int.from_bytes(out.raw, "little")
+
+    def digest(self):
+        out = C.create_string_buffer(32)
+        _check(load_library().zkdl_transcript_digest(self.handle, out), "zkdl_transcript_digest")
+        return out.raw
+
+    def __del__(self):
+        try:
+            if self.handle:
+                load_library().zkdl_transcript_destroy(self.handle)
+                self.handle = C.c_void_p()
+        except Exception:
+            pass
+
+
+class FrTensor:
+    def __init__(self, ctx, handle, keepalive=None):
+        self.ctx = ctx
+        self.handle = handle
+        self._keepalive = keepalive
+
+    @property
+    def shape(self):
+        lib = load_library()
+        return tuple(int(lib.zkdl_tensor_dim(self.handle, a)) for a in range(lib.zkdl_tensor_ndim(self.handle)))
+
+    @property
+    def numel(self):
+        return int(load_library().zkdl_tensor_numel(self.handle))
+
+    def download(self):
+        """Canonical little-endian bytes, numel x 32."""
+        out = np.empty(self.numel * 32, dtype=np.uint8)
+        _check(load_library().zkdl_tensor_download(self.ctx.handle, self.handle, out.ctypes.data),
+               "zkdl_tensor_download", self.ctx)
+        return out.tobytes()
+
+    def free(self):
+        if self.handle:
+            load_library().zkdl_tensor_free(self.ctx.handle, self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def _shape_arr(shape):
+    return (C.c_uint64 * len(shape))(*[int(s) for s in shape]), len(shape)
+
+
+def _src_pointer(src):
+    """(pointer, on_device, dtype code, keepalive) for a numpy array, bytes or torch tensor."""
+    try:
+        import torch
+        is_torch = isinstance(src, torch.Tensor)
+    except ImportError:
+        is_torch = False
+    if is_torch:
+        import torch
+        assert src.is_contiguous()
+        code = {torch.int32: ZKDL_I32, torch.int64: ZKDL_I64, torch.uint8: ZKDL_FR_LE}[src.dtype]
+        return src.data_ptr(), 1 if src.is_cuda else 0, code, src
+    if isinstance(src, (bytes, bytearray)):
+        arr = np.frombuffer(bytes(src), dtype=np.uint8)
+        return arr.ctypes.data, 0, ZKDL_FR_LE, arr
+    arr = np.ascontiguousarray(src)
+    code = {np.dtype(np.int32): ZKDL_I32, np.dtype(np.int64): ZKDL_I64, np.dtype(np.uint8): ZKDL_FR_LE,
+            np.dtype(np.uint64): ZKDL_FR_LE}[arr.dtype]
+    return arr.ctypes.data, 0, code, arr
+
+
+def fr_tensor_upload(ctx, src, shape):
+    """int32 / int64 (signed, x mod r) or raw 32-byte little-endian elements
+    (uint8 / uint64 arrays, bytes) -> Fr tensor on the device."""
+    ptr, on_dev, code, keep = _src_pointer(src)
+    sh, nd = _shape_arr(shape)
+    out = C.c_void_p()
+    _check(load_library().fr_tensor_upload(ctx.handle, ptr, code, on_dev, sh, nd, C.byref(out)),
+           "fr_tensor_upload", ctx)
+    return FrTensor(ctx, out)
+
+
+def tensor_wrap_int(ctx, torch_tensor, shape=None):
+    """A no-copy view of an int32/int64 CUDA tensor (kept alive by the result)."""
+    ptr, on_dev, code, keep = _src_pointer(torch_tensor)
+    assert on_dev and code in (ZKDL_I32, ZKDL_I64)
+    sh, nd = _shape_arr(shape if shape is not None else tuple(torch_tensor.shape))
+    out = C.c_void_p()
+    _check(load_library().zkdl_tensor_wrap_int(ctx.handle, ptr, code, sh, nd, C.byref(out)),
+           "zkdl_tensor_wrap_int", ctx)
+    return FrTensor(ctx, out, keepalive=keep)
+
+
+def _fr_bytes(values):
+    return b"".join(int(v).to_bytes(32, "little") for v in values)
+
+
+def _split_fr(buf, n):
+    return [int.from_bytes(buf[32 * k:32 * k + 32], "little") for k in range(n)]
+
+
+def mle_partial_eval(ctx, t, axis_lo, axis_hi, point):
+    pb = _fr_bytes(point)
+    buf = C.create_string_buffer(pb, max(len(pb), 1))
+    out = C.c_void_p()
+    _check(load_library().mle_partial_eval(ctx.handle, t.handle, axis_lo, axis_hi, buf, len(point),
+                                           C.byref(out)), "mle_partial_eval", ctx)
+    return FrTensor(ctx, out)
+
+
+class _Outputs:
+    def __init__(self, n_claims):
+        self.proof = C.create_string_buffer(PROOF_CAP)
+        self.proof_len = C.c_size_t(PROOF_CAP)
+        self.claims = C.create_string_buffer(32 * max(n_claims, 1))
+        self.points = C.create_string_buffer(32 * POINTS_CAP)
+        self.npoints = C.c_size_t(POINTS_CAP)
+        self.n_claims = n_claims
+
+    def result(self):
+        return dict(proof=self.proof.raw[:self.proof_len.value],
+                    claims=_split_fr(self.claims.raw, self.n_claims),
+                    points=_split_fr(self.points.raw, self.npoints.value))
+
+
+def sumcheck_product(ctx, tables, tr):
+    k = len(tables)
+    arr = (C.c_void_p * k)(*[t.handle for t in tables])
+    o = _Outputs(k)
+    _check(load_library().sumcheck_product(ctx.handle, arr, k, tr.handle, o.proof, C.byref(o.proof_len),
+                                           o.claims, o.points, C.byref(o.npoints)), "sumcheck_product", ctx)
+    return o.result()
+
+
+def sumcheck_matmul(ctx, x0, x1, tr, transpose_x0=False, transpose_x1=False):
+    o = _Outputs(3)
+    _check(load_library().sumcheck_matmul(ctx.handle, x0.handle, x1.handle, int(transpose_x0),
+                                          int(transpose_x1), tr.handle, o.proof, C.byref(o.proof_len),
+                                          o.claims, o.points, C.byref(o.npoints)), "sumcheck_matmul", ctx)
+    return o.result()
+
+
+def sumcheck_hadamard(ctx, x0, x1, tr):
+    o = _Outputs(3)
+    _check(load_library().sumcheck_hadamard(ctx.handle, x0.handle, x1.handle, tr.handle, o.proof,
+                                            C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
+           "sumcheck_hadamard", ctx)
+    return o.result()
+
+
+def zkrelu_prove(ctx, z, ga, tr, q=32, r=16):
+    """z, ga: int64 numpy arrays (host) or int64 CUDA tensors; ga may be None."""
+    zp, z_dev, zc, zk_ = _src_pointer(z)
+    assert zc == ZKDL_I64
+    d = int(np.prod(z.shape))
+    gp = None
+    if ga is not None:
+        gp, g_dev, gc, gk_ = _src_pointer(ga)
+        assert gc == ZKDL_I64 and g_dev == z_dev
+    o = _Outputs(4)
+    _check(load_library().zkrelu_prove(ctx.handle, zp, gp, d, q, r, z_dev, tr.handle, o.proof,
+                                       C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
+           "zkrelu_prove", ctx)
+    return o.result()
+
+
+def aggregate_prove(ctx, wit, tr):
+    """wit: dict with L, B, width, T, Q, R and CUDA tensors A, W, GZ (int32), Zr, GA (int64)."""
+    import torch
+    for k, dt in (("A", torch.int32), ("W", torch.int32), ("GZ", torch.int32), ("Zr", torch.int64),
+                  ("GA", torch.int64)):
+        assert wit[k].is_cuda and wit[k].dtype == dt and wit[k].is_contiguous()
+    n = wit["L"] * wit["T"]
+    assert wit["A"].numel() == n * wit["B"] * wit["width"] == wit["GZ"].numel() == wit["Zr"].numel() \
+        == wit["GA"].numel() and wit["W"].numel() == n * wit["width"] ** 2
+    w = FcnnWitness(wit["L"], wit["B"], wit["width"], wit["T"], wit["Q"], wit["R"],
+                    wit["A"].data_ptr(), wit["W"].data_ptr(), wit["GZ"].data_ptr(), wit["Zr"].data_ptr(),
+                    wit["GA"].data_ptr())
+    o = _Outputs(0)
+    _check(load_library().aggregate_prove(ctx.handle, C.byref(w), tr.handle, o.proof, C.byref(o.proof_len),
+                                          o.points, C.byref(o.npoints)), "aggregate_prove", ctx)
+    return o.result()
+
+
+def host_fr_mul(a, b):
+    out = C.create_string_buffer(32)
+    _check(load_library().zkdl_host_fr_mul(C.create_string_buffer(int(a).to_bytes(32, "little"), 32),
+                                           C.create_string_buffer(int(b).to_bytes(32, "little"), 32), out),
+           "zkdl_host_fr_mul")
+    return int.from_bytes(out.raw, "little")
+
+
+def selfcheck_constants():
+    return load_library().zkdl_selfcheck_constants()

@@ -1,0 +1,793 @@
+// C ABI of the library: contexts, transcripts, tensors and the host-side
+// orchestration of each proof (which kernels run, in which order, on the
+// context's stream).  See include/zkdl.h for the contract of every entry point.
+#include <string.h>
+#include <new>
+
+#include "zkdl_internal.h"
+
+// ---------------------------------------------------------------------------
+// scratch allocator: hipMalloc with a cache of freed blocks.  All work of a
+// context is on one stream, so a block may be handed out again as soon as the
+// host has released it: the kernels that used it are ahead in the stream.
+// ---------------------------------------------------------------------------
+void* zk_alloc(zkdl_ctx* ctx, size_t bytes) {
+    if (bytes == 0) bytes = 256;
+    bytes = (bytes + 255) & ~(size_t)255;
+    auto it = ctx->free_blocks.lower_bound(bytes);
+    if (it != ctx->free_blocks.end() && it->first <= bytes * 2) {
+        void* p = it->second;
+        ctx->live_blocks[p] = it->first;
+        ctx->free_blocks.erase(it);
+        return p;
+    }
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+        // give cached memory back and retry once
+        zkdl_ctx_trim(ctx);
+        e = hipMalloc(&p, bytes);
+        if (e != hipSuccess) {
+            ctx->last_hip = (int)e;
+            (void)hipGetLastError();
+            return nullptr;
+        }
+    }
+    ctx->live_blocks[p] = bytes;
+    return p;
+}
+
+void zk_free(zkdl_ctx* ctx, void* p) {
+    if (!p) return;
+    auto it = ctx->live_blocks.find(p);
+    if (it == ctx->live_blocks.end()) return;
+    ctx->free_blocks.insert({it->second, p});
+    ctx->live_blocks.erase(it);
+}
+
+extern "C" int zkdl_ctx_trim(zkdl_ctx* ctx) {
+    if (!ctx) return ZKDL_EINVAL;
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto& kv : ctx->free_blocks) (void)hipFree(kv.second);
+    ctx->free_blocks.clear();
+    return ZKDL_OK;
+}
+
+// ---------------------------------------------------------------------------
+// constants
+// ---------------------------------------------------------------------------
+static Fr host_double_mod(const Fr& a) { return fr_add(a, a); }
+
+extern "C" int zkdl_selfcheck_constants(void) {
+    // 2^256, 2^512, 2^768 mod r by repeated doubling of 1
+    Fr x = fr_zero();
+    x.v[0] = 1;
+    for (int i = 0; i < 256; ++i) x = host_double_mod(x);
+    if (!fr_eq(x, fr_const(frc::ONE))) return ZKDL_EINVAL;
+    for (int i = 0; i < 256; ++i) x = host_double_mod(x);
+    if (!fr_eq(x, fr_const(frc::R2))) return ZKDL_EINVAL;
+    for (int i = 0; i < 256; ++i) x = host_double_mod(x);
+    if (!fr_eq(x, fr_const(frc::R3))) return ZKDL_EINVAL;
+    // the modulus is 1 mod 2^32, which the reduction step of fr_mul relies on
+    if (frc::MOD[0] != 1u) return ZKDL_EINVAL;
+    return ZKDL_OK;
+}
+
+static Fr host_inverse(const Fr& a_mont) {
+    uint32_t e[8];
+    for (int i = 0; i < 8; ++i) e[i] = frc::MOD[i];
+    // exponent r - 2 (Fermat); r[0] = 1, so the subtraction borrows from the next limb
+    e[0] = 0xffffffffu;
+    int k = 1;
+    while (e[k] == 0) {
+        e[k] = 0xffffffffu;
+        ++k;
+    }
+    e[k] -= 1;
+    return fr_pow(a_mont, e);
+}
+
+extern "C" int zkdl_host_fr_mul(const zkdl_fr* a, const zkdl_fr* b, zkdl_fr* out) {
+    if (!a || !b || !out) return ZKDL_EINVAL;
+    Fr x, y;
+    memcpy(x.v, a->le, 32);
+    memcpy(y.v, b->le, 32);
+    Fr p = fr_mul(fr_to_mont(x), fr_to_mont(y));
+    Fr plain = fr_from_mont(p);
+    memcpy(out->le, plain.v, 32);
+    return ZKDL_OK;
+}
+
+// ---------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------
+extern "C" const char* zkdl_strerror(int err) {
+    switch (err) {
+        case ZKDL_OK: return "ok";
+        case ZKDL_EINVAL: return "invalid argument";
+        case ZKDL_ERANGE: return "zkReLU input outside the (Q+R)-bit range";
+        case ZKDL_ENOMEM: return "out of memory";
+        case ZKDL_EHIP: return "HIP runtime error";
+        case ZKDL_ESMALL: return "output buffer too small";
+        default: return "unknown error";
+    }
+}
+
+extern "C" int zkdl_ctx_create(zkdl_ctx** out, int device, void* hip_stream) {
+    if (!out) return ZKDL_EINVAL;
+    *out = nullptr;
+    if (zkdl_selfcheck_constants() != ZKDL_OK) return ZKDL_EINVAL;
+    zkdl_ctx* ctx = new (std::nothrow) zkdl_ctx();
+    if (!ctx) return ZKDL_ENOMEM;
+    ctx->device = device;
+    ctx->stream = (hipStream_t)hip_stream;
+    ctx->last_hip = 0;
+    ctx->dev = nullptr;
+    ctx->host_stage = nullptr;
+    ctx->partials = nullptr;
+    ctx->n_chal = 0;
+    ctx->proof_len = 0;
+    hipError_t e = hipSetDevice(device);
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->dev, sizeof(DevState));
+    if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->host_stage, sizeof(DevState), hipHostMallocDefault);
+    if (e == hipSuccess)
+        e = hipMalloc((void**)&ctx->partials, sizeof(Fr) * ZK_MAX_PART_BLOCKS * ZK_MAX_EVALS * 2);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->dev, 0, sizeof(DevState), ctx->stream);
+    if (e == hipSuccess) {
+        // constants of the Lagrange formulas
+        Fr two = fr_add(fr_one(), fr_one());
+        Fr six = fr_add(fr_add(two, two), two);
+        Fr c[2] = {host_inverse(two), host_inverse(six)};
+        if (!fr_eq(fr_mul(c[0], two), fr_one()) || !fr_eq(fr_mul(c[1], six), fr_one())) {
+            e = hipErrorUnknown;
+        } else {
+            memcpy(ctx->host_stage, c, sizeof(c));
+            e = hipMemcpyAsync(&ctx->dev->inv2, ctx->host_stage, sizeof(c), hipMemcpyHostToDevice,
+                               ctx->stream);
+            if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        }
+    }
+    if (e != hipSuccess) {
+        int code = (int)e;
+        (void)hipGetLastError();
+        if (ctx->dev) (void)hipFree(ctx->dev);
+        if (ctx->host_stage) (void)hipHostFree(ctx->host_stage);
+        if (ctx->partials) (void)hipFree(ctx->partials);
+        delete ctx;
+        (void)code;
+        return ZKDL_EHIP;
+    }
+    *out = ctx;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_ctx_destroy(zkdl_ctx* ctx) {
+    if (!ctx) return ZKDL_EINVAL;
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto& kv : ctx->free_blocks) (void)hipFree(kv.second);
+    for (auto& kv : ctx->live_blocks) (void)hipFree(kv.first);
+    (void)hipFree(ctx->dev);
+    (void)hipHostFree(ctx->host_stage);
+    (void)hipFree(ctx->partials);
+    delete ctx;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_last_hip_error(const zkdl_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+// ---------------------------------------------------------------------------
+// transcript (host)
+// ---------------------------------------------------------------------------
+extern "C" int zkdl_transcript_create(zkdl_transcript** out, uint64_t seed) {
+    if (!out) return ZKDL_EINVAL;
+    zkdl_transcript* t = new (std::nothrow) zkdl_transcript();
+    if (!t) return ZKDL_ENOMEM;
+    static const char dom[] = "zkdl-mi355x/v1";
+    uint8_t buf[64];
+    uint32_t p = 0;
+    for (size_t i = 0; i < sizeof(dom) - 1; ++i) buf[p++] = (uint8_t)dom[i];
+    for (int i = 0; i < 8; ++i) buf[p++] = (uint8_t)(seed >> (8 * i));
+    sha::digest_inplace(buf, p, t->state);
+    *out = t;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_transcript_destroy(zkdl_transcript* t) {
+    if (!t) return ZKDL_EINVAL;
+    delete t;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_transcript_absorb(zkdl_transcript* t, const char* label, const void* bytes, size_t n) {
+    if (!t || !label || (!bytes && n) || n > 0x7fffffffu) return ZKDL_EINVAL;
+    size_t ll = strlen(label);
+    if (ll > ts::MAX_LABEL) return ZKDL_EINVAL;
+    std::vector<uint8_t> buf(ts::scratch_bytes((uint32_t)n));
+    ts::absorb(t->state, label, (uint32_t)ll, (const uint8_t*)bytes, (uint32_t)n, buf.data());
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_transcript_challenge(zkdl_transcript* t, zkdl_fr* host_out) {
+    if (!t || !host_out) return ZKDL_EINVAL;
+    ts::challenge(t->state, host_out->le);
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_transcript_digest(const zkdl_transcript* t, uint8_t host_out[32]) {
+    if (!t || !host_out) return ZKDL_EINVAL;
+    memcpy(host_out, t->state, 32);
+    return ZKDL_OK;
+}
+
+// ---------------------------------------------------------------------------
+// tensors
+// ---------------------------------------------------------------------------
+static bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
+static int ilog2_u64(uint64_t x) {
+    int l = 0;
+    while (((uint64_t)1 << l) < x) ++l;
+    return l;
+}
+
+static int check_shape(const uint64_t* shape, int ndim, uint64_t* numel) {
+    if (ndim < 0 || ndim > ZKDL_MAX_DIMS || (ndim > 0 && !shape)) return ZKDL_EINVAL;
+    uint64_t n = 1;
+    for (int i = 0; i < ndim; ++i) {
+        if (!is_pow2(shape[i])) return ZKDL_EINVAL;
+        if (n > ((uint64_t)1 << 40) / shape[i]) return ZKDL_EINVAL;
+        n *= shape[i];
+    }
+    *numel = n;
+    return ZKDL_OK;
+}
+
+static zkdl_tensor* new_tensor(int kind, const uint64_t* shape, int ndim, uint64_t numel) {
+    zkdl_tensor* t = new (std::nothrow) zkdl_tensor();
+    if (!t) return nullptr;
+    t->kind = kind;
+    t->ndim = ndim;
+    for (int i = 0; i < ZKDL_MAX_DIMS; ++i) t->shape[i] = i < ndim ? shape[i] : 1;
+    t->numel = numel;
+    t->data = nullptr;
+    t->owned = false;
+    return t;
+}
+
+static size_t dtype_size(int dtype) { return dtype == ZKDL_I32 ? 4 : dtype == ZKDL_I64 ? 8 : 32; }
+
+extern "C" int fr_tensor_upload(zkdl_ctx* ctx, const void* src, int dtype, int src_on_device,
+                                const uint64_t* shape, int ndim, zkdl_tensor** out) {
+    if (!ctx || !src || !out) return ZKDL_EINVAL;
+    if (dtype != ZKDL_I32 && dtype != ZKDL_I64 && dtype != ZKDL_FR_LE) return ZKDL_EINVAL;
+    uint64_t n;
+    int rc = check_shape(shape, ndim, &n);
+    if (rc != ZKDL_OK) return rc;
+    zkdl_tensor* t = new_tensor(TK_FR, shape, ndim, n);
+    if (!t) return ZKDL_ENOMEM;
+    t->data = zk_alloc(ctx, n * 32);
+    if (!t->data) {
+        delete t;
+        return ZKDL_ENOMEM;
+    }
+    t->owned = true;
+    const void* dsrc = src;
+    void* staged = nullptr;
+    if (!src_on_device) {
+        staged = zk_alloc(ctx, n * dtype_size(dtype));
+        if (!staged) {
+            zk_free(ctx, t->data);
+            delete t;
+            return ZKDL_ENOMEM;
+        }
+        hipError_t e = hipMemcpyAsync(staged, src, n * dtype_size(dtype), hipMemcpyHostToDevice, ctx->stream);
+        if (e != hipSuccess) {
+            ctx->last_hip = (int)e;
+            zk_free(ctx, staged);
+            zk_free(ctx, t->data);
+            delete t;
+            return ZKDL_EHIP;
+        }
+        dsrc = staged;
+    }
+    int kind = dtype == ZKDL_I32 ? TK_I32 : dtype == ZKDL_I64 ? TK_I64 : 3;
+    zk_launch_convert(ctx, dsrc, kind, n, make_tab(t->data, n));
+    if (staged) {
+        // the host buffer is pageable: make sure the copy has consumed it before returning
+        ZK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        zk_free(ctx, staged);
+    }
+    ZK_HIP(ctx, hipGetLastError());
+    *out = t;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_tensor_wrap_int(zkdl_ctx* ctx, const void* device_src, int dtype,
+                                    const uint64_t* shape, int ndim, zkdl_tensor** out) {
+    if (!ctx || !device_src || !out) return ZKDL_EINVAL;
+    if (dtype != ZKDL_I32 && dtype != ZKDL_I64) return ZKDL_EINVAL;
+    uint64_t n;
+    int rc = check_shape(shape, ndim, &n);
+    if (rc != ZKDL_OK) return rc;
+    zkdl_tensor* t = new_tensor(dtype == ZKDL_I32 ? TK_I32 : TK_I64, shape, ndim, n);
+    if (!t) return ZKDL_ENOMEM;
+    t->data = const_cast<void*>(device_src);
+    *out = t;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_tensor_ndim(const zkdl_tensor* t) { return t ? t->ndim : -1; }
+extern "C" uint64_t zkdl_tensor_dim(const zkdl_tensor* t, int axis) {
+    return (t && axis >= 0 && axis < t->ndim) ? t->shape[axis] : 0;
+}
+extern "C" uint64_t zkdl_tensor_numel(const zkdl_tensor* t) { return t ? t->numel : 0; }
+
+extern "C" int zkdl_tensor_free(zkdl_ctx* ctx, zkdl_tensor* t) {
+    if (!ctx || !t) return ZKDL_EINVAL;
+    if (t->owned) zk_free(ctx, t->data);
+    delete t;
+    return ZKDL_OK;
+}
+
+// an Fr view of any tensor: Fr tensors as they are, integer tensors converted into scratch
+struct FrView {
+    FrTab tab;
+    void* scratch;
+};
+
+static int as_fr(zkdl_ctx* ctx, const zkdl_tensor* t, FrView* v) {
+    v->scratch = nullptr;
+    if (t->kind == TK_FR) {
+        v->tab = make_tab(t->data, t->numel);
+        return ZKDL_OK;
+    }
+    v->scratch = zk_alloc(ctx, t->numel * 32);
+    if (!v->scratch) return ZKDL_ENOMEM;
+    v->tab = make_tab(v->scratch, t->numel);
+    zk_launch_convert(ctx, t->data, t->kind, t->numel, v->tab);
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_tensor_download(zkdl_ctx* ctx, const zkdl_tensor* t, zkdl_fr* host_out) {
+    if (!ctx || !t || !host_out) return ZKDL_EINVAL;
+    FrView v;
+    int rc = as_fr(ctx, t, &v);
+    if (rc != ZKDL_OK) return rc;
+    void* le = zk_alloc(ctx, t->numel * 32);
+    if (!le) {
+        zk_free(ctx, v.scratch);
+        return ZKDL_ENOMEM;
+    }
+    zk_launch_download(ctx, v.tab, t->numel, (uint8_t*)le);
+    hipError_t e = hipMemcpyAsync(host_out, le, t->numel * 32, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    zk_free(ctx, le);
+    zk_free(ctx, v.scratch);
+    ZK_HIP(ctx, e);
+    return ZKDL_OK;
+}
+
+// ---------------------------------------------------------------------------
+// call framing: transcript state to the device, proof and challenges back
+// ---------------------------------------------------------------------------
+struct HeaderPatch {
+    size_t off;
+    uint32_t words[8];
+    int n;
+};
+static thread_local std::vector<HeaderPatch> g_patches;
+
+void zk_write_proof_words(zkdl_ctx* ctx, const uint32_t* words, int n) {
+    HeaderPatch p;
+    p.off = ctx->proof_len;
+    p.n = n;
+    for (int i = 0; i < n; ++i) p.words[i] = words[i];
+    g_patches.push_back(p);
+    ctx->proof_len += 4 * (size_t)n;
+}
+
+struct AbsorbWordsArg {
+    char label[32];
+    uint32_t label_len;
+    uint32_t words[8];
+    uint32_t n;
+};
+
+__global__ void k_absorb_words(DevState* st, AbsorbWordsArg a) {
+    __shared__ uint8_t lds[256];
+    if (threadIdx.x != 0) return;
+    uint8_t data[32];
+    for (uint32_t i = 0; i < a.n; ++i)
+        for (int b = 0; b < 4; ++b) data[4 * i + b] = (uint8_t)(a.words[i] >> (8 * b));
+    uint8_t state[32];
+    for (int i = 0; i < 32; ++i) state[i] = st->ts_state[i];
+    ts::absorb(state, a.label, a.label_len, data, 4 * a.n, lds);
+    for (int i = 0; i < 32; ++i) st->ts_state[i] = state[i];
+}
+
+// header of a protocol: a label and up to 8 little-endian u32 words, absorbed in stream order
+static void dev_absorb_words(zkdl_ctx* ctx, const char* label, const uint32_t* words, int n) {
+    AbsorbWordsArg a;
+    a.label_len = 0;
+    while (label[a.label_len] && a.label_len < 31) {
+        a.label[a.label_len] = label[a.label_len];
+        ++a.label_len;
+    }
+    a.n = (uint32_t)n;
+    for (int i = 0; i < n; ++i) a.words[i] = words[i];
+    hipLaunchKernelGGL(k_absorb_words, dim3(1), dim3(64), 0, ctx->stream, ctx->dev, a);
+}
+
+static int call_begin(zkdl_ctx* ctx, zkdl_transcript* tr) {
+    ZK_HIP(ctx, hipSetDevice(ctx->device));
+    ctx->n_chal = 0;
+    ctx->proof_len = 0;
+    g_patches.clear();
+    // state + cleared error word
+    memset(ctx->host_stage, 0, 64);
+    memcpy(ctx->host_stage, tr->state, 32);
+    ZK_HIP(ctx, hipMemcpyAsync(ctx->dev, ctx->host_stage, 64, hipMemcpyHostToDevice, ctx->stream));
+    return ZKDL_OK;
+}
+
+static int call_end(zkdl_ctx* ctx, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+                    zkdl_fr* points_out, size_t* npoints, const int* scal_ids, int n_scal,
+                    zkdl_fr* scal_out) {
+    ZK_HIP(ctx, hipGetLastError());
+    uint8_t* hs = ctx->host_stage;
+    // layout of the staging buffer mirrors DevState
+    ZK_HIP(ctx, hipMemcpyAsync(hs, ctx->dev, offsetof(DevState, chal), hipMemcpyDeviceToHost, ctx->stream));
+    if (ctx->n_chal > 0)
+        ZK_HIP(ctx, hipMemcpyAsync(hs + offsetof(DevState, chal_le), ctx->dev->chal_le,
+                                   32 * (size_t)ctx->n_chal, hipMemcpyDeviceToHost, ctx->stream));
+    if (ctx->proof_len > 0)
+        ZK_HIP(ctx, hipMemcpyAsync(hs + offsetof(DevState, proof), ctx->dev->proof, ctx->proof_len,
+                                   hipMemcpyDeviceToHost, ctx->stream));
+    ZK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    const DevState* h = (const DevState*)hs;
+    if (h->err & 1u) return ZKDL_ERANGE;
+    memcpy(tr->state, h->ts_state, 32);
+    int rc = ZKDL_OK;
+    if (proof_len) {
+        if (!proof || *proof_len < ctx->proof_len) {
+            rc = ZKDL_ESMALL;
+        } else {
+            memcpy(proof, h->proof, ctx->proof_len);
+            for (const HeaderPatch& p : g_patches)
+                for (int i = 0; i < p.n; ++i)
+                    for (int b = 0; b < 4; ++b) proof[p.off + 4 * i + b] = (uint8_t)(p.words[i] >> (8 * b));
+        }
+        *proof_len = ctx->proof_len;
+    }
+    if (points_out && npoints) {
+        if (*npoints < (size_t)ctx->n_chal) rc = ZKDL_ESMALL;
+        else memcpy(points_out, h->chal_le, 32 * (size_t)ctx->n_chal);
+    }
+    if (npoints) *npoints = (size_t)ctx->n_chal;
+    for (int i = 0; i < n_scal && scal_out; ++i) {
+        Fr plain = fr_from_mont(h->scal[scal_ids[i]]);
+        memcpy(scal_out[i].le, plain.v, 32);
+    }
+    return rc;
+}
+
+// ---------------------------------------------------------------------------
+// mle_partial_eval
+// ---------------------------------------------------------------------------
+extern "C" int mle_partial_eval(zkdl_ctx* ctx, const zkdl_tensor* t, int axis_lo, int axis_hi,
+                                const zkdl_fr* point, size_t npoint, zkdl_tensor** out) {
+    if (!ctx || !t || !out || axis_lo < 0 || axis_hi < axis_lo || axis_hi > t->ndim) return ZKDL_EINVAL;
+    if (npoint && !point) return ZKDL_EINVAL;
+    uint64_t O = 1, A = 1, I = 1;
+    for (int i = 0; i < axis_lo; ++i) O *= t->shape[i];
+    for (int i = axis_lo; i < axis_hi; ++i) A *= t->shape[i];
+    for (int i = axis_hi; i < t->ndim; ++i) I *= t->shape[i];
+    int m = ilog2_u64(A);
+    if ((size_t)m != npoint || m > 40) return ZKDL_EINVAL;
+    ZK_HIP(ctx, hipSetDevice(ctx->device));
+    uint64_t oshape[ZKDL_MAX_DIMS];
+    int ond = 0;
+    for (int i = 0; i < axis_lo; ++i) oshape[ond++] = t->shape[i];
+    for (int i = axis_hi; i < t->ndim; ++i) oshape[ond++] = t->shape[i];
+    zkdl_tensor* o = new_tensor(TK_FR, oshape, ond, O * I);
+    if (!o) return ZKDL_ENOMEM;
+    o->data = zk_alloc(ctx, O * I * 32);
+    o->owned = true;
+    size_t pbytes = (size_t)(m > 0 ? m : 1) * 32;
+    uint8_t* ple = (uint8_t*)zk_alloc(ctx, pbytes);
+    Fr* pm = (Fr*)zk_alloc(ctx, pbytes);
+    void* beta = zk_alloc(ctx, A * 32);
+    int rc = (o->data && ple && pm && beta) ? ZKDL_OK : ZKDL_ENOMEM;
+    if (rc == ZKDL_OK && m > 0) {
+        hipError_t e = hipMemcpyAsync(ple, point, (size_t)m * 32, hipMemcpyHostToDevice, ctx->stream);
+        if (e != hipSuccess) {
+            ctx->last_hip = (int)e;
+            rc = ZKDL_EHIP;
+        }
+    }
+    if (rc == ZKDL_OK) {
+        zk_launch_points_to_mont(ctx, ple, m, pm);
+        FrTab bt = make_tab(beta, A);
+        rc = zk_build_beta(ctx, pm, m, bt);
+        if (rc == ZKDL_OK) {
+            FrTab src_tab = make_tab(t->data, t->numel);
+            const void* src = t->kind == TK_FR ? (const void*)&src_tab : t->data;
+            rc = zk_partial_eval(ctx, t->kind, src, O, A, I, bt, make_tab(o->data, O * I));
+        }
+    }
+    hipError_t e = hipStreamSynchronize(ctx->stream);   // `point` is pageable host memory
+    zk_free(ctx, ple);
+    zk_free(ctx, pm);
+    zk_free(ctx, beta);
+    if (rc == ZKDL_OK && e != hipSuccess) {
+        ctx->last_hip = (int)e;
+        rc = ZKDL_EHIP;
+    }
+    if (rc == ZKDL_OK && (e = hipGetLastError()) != hipSuccess) {
+        ctx->last_hip = (int)e;
+        rc = ZKDL_EHIP;
+    }
+    if (rc != ZKDL_OK) {
+        zkdl_tensor_free(ctx, o);
+        return rc;
+    }
+    *out = o;
+    return ZKDL_OK;
+}
+
+// ---------------------------------------------------------------------------
+// sumcheck_product
+// ---------------------------------------------------------------------------
+extern "C" int sumcheck_product(zkdl_ctx* ctx, const zkdl_tensor* const* tables, int K,
+                                zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+                                zkdl_fr* finals, zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !tables || !tr || K < 1 || K > 3) return ZKDL_EINVAL;
+    for (int k = 0; k < K; ++k)
+        if (!tables[k] || tables[k]->numel != tables[0]->numel) return ZKDL_EINVAL;
+    const uint64_t n = tables[0]->numel;
+    const int d = ilog2_u64(n);
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    uint32_t hdr[2] = {(uint32_t)K, (uint32_t)d};
+    dev_absorb_words(ctx, "sumcheck_product", hdr, 2);
+    FrView views[3];
+    FrTab src[3], work[3];
+    void* wmem = nullptr;
+    for (int k = 0; k < K; ++k) views[k].scratch = nullptr;
+    for (int k = 0; k < K && rc == ZKDL_OK; ++k) {
+        rc = as_fr(ctx, tables[k], &views[k]);
+        src[k] = views[k].tab;
+    }
+    const uint64_t half = n > 1 ? n / 2 : 1;
+    if (rc == ZKDL_OK) {
+        wmem = zk_alloc(ctx, (size_t)K * half * 32);
+        if (!wmem) rc = ZKDL_ENOMEM;
+    }
+    if (rc == ZKDL_OK) {
+        for (int k = 0; k < K; ++k) work[k] = make_tab((uint32_t*)wmem + (size_t)k * half * 8, half);
+        rc = zk_sumcheck_product(ctx, K, src, work, d, 0);
+    }
+    int ids[3] = {0, 1, 2};
+    int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, ids, K, finals);
+    zk_free(ctx, wmem);
+    for (int k = 0; k < K; ++k) zk_free(ctx, views[k].scratch);
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
+// ---------------------------------------------------------------------------
+// matmul / Hadamard (Eqs. exm-matmul-batched, exm-hadamard-batched)
+// ---------------------------------------------------------------------------
+struct MatmulShape {
+    uint64_t N, D1, D2, D3;
+};
+
+// Enqueues one matmul sumcheck.  X0 stored [N, r0, c0], X1 stored [N, r1, c1].
+// shift != 0: stack slot n uses slot n+1 of both operands, zero in the last slot of
+// every `shift`-slot period (the gradA family).  Final claims are left in
+// scal[scal_base .. +3): beta~(w,v_n), X0~, X1~.
+static int enqueue_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1, int tr0, int tr1,
+                          uint32_t shift, int scal_base, MatmulShape* shp_out) {
+    if (X0->ndim != 3 || X1->ndim != 3 || X0->shape[0] != X1->shape[0]) return ZKDL_EINVAL;
+    const uint64_t N = X0->shape[0];
+    const uint64_t D1 = tr0 ? X0->shape[2] : X0->shape[1];
+    const uint64_t D2 = tr0 ? X0->shape[1] : X0->shape[2];
+    const uint64_t D2b = tr1 ? X1->shape[2] : X1->shape[1];
+    const uint64_t D3 = tr1 ? X1->shape[1] : X1->shape[2];
+    if (D2 != D2b) return ZKDL_EINVAL;
+    if (shp_out) *shp_out = MatmulShape{N, D1, D2, D3};
+    const int ln = ilog2_u64(N), l1 = ilog2_u64(D1), l2 = ilog2_u64(D2), l3 = ilog2_u64(D3);
+    if (ctx->n_chal + ln + l1 + l3 + ln + l2 > ZK_MAX_CHAL) return ZKDL_EINVAL;
+    uint32_t hdr[4] = {(uint32_t)N, (uint32_t)D1, (uint32_t)D2, (uint32_t)D3};
+    dev_absorb_words(ctx, "sumcheck_matmul", hdr, 4);
+    const int cw = ctx->n_chal, cu0 = cw + ln, cu1 = cu0 + l1;
+    zk_launch_draw(ctx, cw, ln + l1 + l3);
+    ctx->n_chal += ln + l1 + l3;
+    const Fr* chal = ctx->dev->chal;
+
+    const uint64_t len = N * D2;
+    const uint64_t half = len > 1 ? len / 2 : 1;
+    const uint64_t bmax = D1 > D3 ? D1 : D3;
+    // scratch: beta tables (N, max(D1,D3)), three source tables, one shift temp, three work tables
+    void* mem = zk_alloc(ctx, (N + bmax + 4 * len + 3 * half) * 32);
+    if (!mem) return ZKDL_ENOMEM;
+    uint32_t* base = (uint32_t*)mem;
+    FrTab bw = make_tab(base, N);
+    base += 8 * N;
+    FrTab bu = make_tab(base, bmax);
+    base += 8 * bmax;
+    FrTab src[3], work[3];
+    for (int k = 0; k < 3; ++k) {
+        src[k] = make_tab(base, len);
+        base += 8 * len;
+    }
+    FrTab tmp = make_tab(base, len);
+    base += 8 * len;
+    for (int k = 0; k < 3; ++k) {
+        work[k] = make_tab(base, half);
+        base += 8 * half;
+    }
+    int rc = zk_build_beta(ctx, chal + cw, ln, bw);
+    if (rc == ZKDL_OK) zk_launch_broadcast_rows(ctx, bw, N, D2, src[0]);
+    // T0[n, i] = X0~(n, u0, i): bind the D1 axis of op(X0)
+    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, chal + cu0, l1, bu);
+    if (rc == ZKDL_OK) {
+        FrTab s0 = make_tab(X0->data, X0->numel);
+        const void* sp = X0->kind == TK_FR ? (const void*)&s0 : X0->data;
+        FrTab dst = shift ? tmp : src[1];
+        if (!tr0) rc = zk_partial_eval(ctx, X0->kind, sp, N, D1, D2, bu, dst);       // stored [N, D1, D2]
+        else rc = zk_partial_eval(ctx, X0->kind, sp, N * D2, D1, 1, bu, dst);        // stored [N, D2, D1]
+        if (rc == ZKDL_OK && shift) zk_launch_shift_rows(ctx, tmp, N, D2, shift, src[1]);
+    }
+    // T1[n, i] = X1~(n, i, u1): bind the D3 axis of op(X1)
+    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, chal + cu1, l3, bu);
+    if (rc == ZKDL_OK) {
+        FrTab s1 = make_tab(X1->data, X1->numel);
+        const void* sp = X1->kind == TK_FR ? (const void*)&s1 : X1->data;
+        FrTab dst = shift ? tmp : src[2];
+        if (!tr1) rc = zk_partial_eval(ctx, X1->kind, sp, N * D2, D3, 1, bu, dst);   // stored [N, D2, D3]
+        else rc = zk_partial_eval(ctx, X1->kind, sp, N, D3, D2, bu, dst);            // stored [N, D3, D2]
+        if (rc == ZKDL_OK && shift) zk_launch_shift_rows(ctx, tmp, N, D2, shift, src[2]);
+    }
+    if (rc == ZKDL_OK) rc = zk_sumcheck_product(ctx, 3, src, work, ln + l2, scal_base);
+    zk_free(ctx, mem);
+    return rc;
+}
+
+extern "C" int sumcheck_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1,
+                               int transpose_x0, int transpose_x1, zkdl_transcript* tr, uint8_t* proof,
+                               size_t* proof_len, zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !X0 || !X1 || !tr) return ZKDL_EINVAL;
+    if (X0->ndim != 3 || X1->ndim != 3) return ZKDL_EINVAL;
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    rc = enqueue_matmul(ctx, X0, X1, transpose_x0 != 0, transpose_x1 != 0, 0, 0, nullptr);
+    zkdl_fr tmp[3];
+    int ids[3] = {0, 1, 2};
+    int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, ids, 3, tmp);
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims && proof) {
+        memcpy(claims[0].le, proof + 16, 32);   // claim_0 = Y~(w, u0, u1)
+        claims[1] = tmp[1];
+        claims[2] = tmp[2];
+    }
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
+extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1,
+                                 zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+                                 zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !X0 || !X1 || !tr || X0->numel != X1->numel) return ZKDL_EINVAL;
+    const uint64_t n = X0->numel;
+    const int d = ilog2_u64(n);
+    if (2 * d > ZK_MAX_CHAL) return ZKDL_EINVAL;
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    uint32_t hdr[1] = {(uint32_t)d};
+    dev_absorb_words(ctx, "sumcheck_hadamard", hdr, 1);
+    zk_launch_draw(ctx, 0, d);
+    ctx->n_chal = d;
+    FrView v0, v1;
+    v0.scratch = v1.scratch = nullptr;
+    const uint64_t half = n > 1 ? n / 2 : 1;
+    void* mem = zk_alloc(ctx, (n + 3 * half) * 32);
+    if (!mem) rc = ZKDL_ENOMEM;
+    if (rc == ZKDL_OK) rc = as_fr(ctx, X0, &v0);
+    if (rc == ZKDL_OK) rc = as_fr(ctx, X1, &v1);
+    if (rc == ZKDL_OK) {
+        FrTab beta = make_tab(mem, n);
+        rc = zk_build_beta(ctx, ctx->dev->chal, d, beta);
+        FrTab src[3] = {beta, v0.tab, v1.tab};
+        FrTab work[3];
+        for (int k = 0; k < 3; ++k) work[k] = make_tab((uint32_t*)mem + 8 * (n + k * half), half);
+        if (rc == ZKDL_OK) rc = zk_sumcheck_product(ctx, 3, src, work, d, 0);
+    }
+    zkdl_fr tmp[3];
+    int ids[3] = {0, 1, 2};
+    int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, ids, 3, tmp);
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims && proof) {
+        memcpy(claims[0].le, proof + 16, 32);
+        claims[1] = tmp[1];
+        claims[2] = tmp[2];
+    }
+    zk_free(ctx, mem);
+    zk_free(ctx, v0.scratch);
+    zk_free(ctx, v1.scratch);
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
+// ---------------------------------------------------------------------------
+// zkReLU and the aggregated proof
+// ---------------------------------------------------------------------------
+static int stage_ints(zkdl_ctx* ctx, const int64_t* host, uint64_t n, void** dev_out) {
+    *dev_out = zk_alloc(ctx, n * 8);
+    if (!*dev_out) return ZKDL_ENOMEM;
+    hipError_t e = hipMemcpyAsync(*dev_out, host, n * 8, hipMemcpyHostToDevice, ctx->stream);
+    if (e != hipSuccess) {
+        ctx->last_hip = (int)e;
+        return ZKDL_EHIP;
+    }
+    return ZKDL_OK;
+}
+
+static const uint32_t ZKRL_MAGIC = 0x4C524B5Au;
+static const uint32_t ZKAG_MAGIC = 0x47414B5Au;
+
+static int enqueue_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q,
+                          int R) {
+    if (!is_pow2(D) || Q < 1 || R < 1 || Q + R > 64 || Q + R < 2) return ZKDL_EINVAL;
+    uint32_t hw[4] = {(uint32_t)ilog2_u64(D), (uint32_t)Q, (uint32_t)R, ga_dev ? 1u : 0u};
+    dev_absorb_words(ctx, "zkrelu", hw, 4);
+    uint32_t hdr[8] = {ZKRL_MAGIC, hw[0], hw[1], hw[2], hw[3], 0, 0, 0};
+    zk_write_proof_words(ctx, hdr, 8);
+    return zk_zkrelu(ctx, z_dev, ga_dev, D, Q, R);
+}
+
+extern "C" int zkrelu_prove(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint64_t D, int Q, int R,
+                            int src_on_device, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+                            zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !Z || !tr) return ZKDL_EINVAL;
+    if (!is_pow2(D) || D > ((uint64_t)1 << 30)) return ZKDL_EINVAL;
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    void *zs = nullptr, *gs = nullptr;
+    const int64_t* zd = Z;
+    const int64_t* gd = GA;
+    if (!src_on_device) {
+        rc = stage_ints(ctx, Z, D, &zs);
+        zd = (const int64_t*)zs;
+        if (rc == ZKDL_OK && GA) {
+            rc = stage_ints(ctx, GA, D, &gs);
+            gd = (const int64_t*)gs;
+        }
+    }
+    if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, zd, gd, D, Q, R);
+    int ids[4] = {0, 1, 2, 3};
+    int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, ids, 4, claims);
+    zk_free(ctx, zs);
+    zk_free(ctx, gs);
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
+extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr,
+                               uint8_t* proof, size_t* proof_len, zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !w || !tr || !w->A || !w->W || !w->GZ || !w->Zr || !w->GA) return ZKDL_EINVAL;
+    if (!is_pow2(w->L) || !is_pow2(w->B) || !is_pow2(w->width) || !is_pow2(w->T)) return ZKDL_EINVAL;
+    const uint64_t N = (uint64_t)w->L * w->T;
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    uint32_t hw[6] = {w->L, w->B, w->width, w->T, w->Q, w->R};
+    dev_absorb_words(ctx, "aggregate", hw, 6);
+    uint32_t hdr[8] = {ZKAG_MAGIC, w->L, w->B, w->width, w->T, w->Q, w->R, 0};
+    zk_write_proof_words(ctx, hdr, 8);
+    uint64_t sa[3] = {N, w->B, w->width}, sw[3] = {N, w->width, w->width};
+    zkdl_tensor tA = {TK_I32, 3, {sa[0], sa[1], sa[2], 1}, N * w->B * w->width, (void*)w->A, false};
+    zkdl_tensor tG = {TK_I32, 3, {sa[0], sa[1], sa[2], 1}, N * w->B * w->width, (void*)w->GZ, false};
+    zkdl_tensor tW = {TK_I32, 3, {sw[0], sw[1], sw[2], 1}, N * w->width * w->width, (void*)w->W, false};
+    // forward: Z = A W
+    rc = enqueue_matmul(ctx, &tA, &tW, 0, 0, 0, 8, nullptr);
+    // gradA: G_A^(l) = G_Z^(l+1) W^(l+1)T, slot of the last layer zero
+    if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tG, &tW, 0, 1, w->L, 12, nullptr);
+    // gradW: G_W^(l) = A^(l-1)T G_Z^(l)
+    if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tA, &tG, 1, 0, 0, 16, nullptr);
+    if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, w->Zr, w->GA, N * w->B * w->width, (int)w->Q, (int)w->R);
+    int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
+    return rc != ZKDL_OK ? rc : rc2;
+}

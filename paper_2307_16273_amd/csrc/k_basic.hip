@@ -1,0 +1,311 @@
+// Conversion into Fr, equality-polynomial tables, and MLE partial evaluation
+// (Eq. multilinear-extension, Sec. 2.2) for gfx950.
+#include "zkdl_internal.h"
+
+// ---------------------------------------------------------------------------
+// integer / byte sources -> Fr (Montgomery, SoA)
+// ---------------------------------------------------------------------------
+template <int KIND>
+__device__ __forceinline__ Fr load_src(const void* src, uint64_t i) {
+    if (KIND == TK_I32) return fr_from_i64((int64_t)((const int32_t*)src)[i]);
+    if (KIND == TK_I64) return fr_from_i64(((const int64_t*)src)[i]);
+    if (KIND == TK_FR) {
+        // never reached: Fr sources are read through FrTab
+        return fr_zero();
+    }
+    // raw 32-byte little-endian values
+    const uint32_t* p = (const uint32_t*)src + 8 * i;
+    Fr x;
+#pragma unroll
+    for (int l = 0; l < 8; ++l) x.v[l] = p[l];
+    return fr_to_mont(x);
+}
+
+constexpr int KIND_LE = 3;
+
+template <int KIND>
+__global__ __launch_bounds__(ZK_BLOCK) void k_convert(const void* src, uint64_t n, FrTab out) {
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n;
+         i += (uint64_t)gridDim.x * blockDim.x)
+        tab_st(out, i, load_src<KIND>(src, i));
+}
+
+static unsigned grid_for(uint64_t n, unsigned cap = 65536) {
+    uint64_t b = (n + ZK_BLOCK - 1) / ZK_BLOCK;
+    if (b < 1) b = 1;
+    if (b > cap) b = cap;
+    return (unsigned)b;
+}
+
+void zk_launch_convert(zkdl_ctx* ctx, const void* src, int kind, uint64_t n, FrTab out) {
+    unsigned g = grid_for(n);
+    if (kind == TK_I32)
+        hipLaunchKernelGGL(k_convert<TK_I32>, dim3(g), dim3(ZK_BLOCK), 0, ctx->stream, src, n, out);
+    else if (kind == TK_I64)
+        hipLaunchKernelGGL(k_convert<TK_I64>, dim3(g), dim3(ZK_BLOCK), 0, ctx->stream, src, n, out);
+    else
+        hipLaunchKernelGGL(k_convert<KIND_LE>, dim3(g), dim3(ZK_BLOCK), 0, ctx->stream, src, n, out);
+}
+
+__global__ __launch_bounds__(ZK_BLOCK) void k_download(FrTab in, uint64_t n, uint32_t* out) {
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n;
+         i += (uint64_t)gridDim.x * blockDim.x) {
+        Fr x = fr_from_mont(tab_ld(in, i));
+#pragma unroll
+        for (int l = 0; l < 8; ++l) out[8 * i + l] = x.v[l];
+    }
+}
+
+void zk_launch_download(zkdl_ctx* ctx, FrTab in, uint64_t n, uint8_t* out_le_dev) {
+    hipLaunchKernelGGL(k_download, dim3(grid_for(n)), dim3(ZK_BLOCK), 0, ctx->stream, in, n,
+                       (uint32_t*)out_le_dev);
+}
+
+__global__ void k_points_to_mont(const uint32_t* le, int n, Fr* out) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        Fr x;
+#pragma unroll
+        for (int l = 0; l < 8; ++l) x.v[l] = le[8 * i + l];
+        out[i] = fr_to_mont(x);
+    }
+}
+
+void zk_launch_points_to_mont(zkdl_ctx* ctx, const uint8_t* le_dev, int n, Fr* out) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(k_points_to_mont, dim3((n + 63) / 64), dim3(64), 0, ctx->stream,
+                       (const uint32_t*)le_dev, n, out);
+}
+
+// ---------------------------------------------------------------------------
+// beta~(u, .): the multilinear extension of the equality indicator (Sec. 2.2),
+// beta~(u, b) = prod_k (u_k b_k + (1 - u_k)(1 - b_k)), u_0 <-> most significant bit.
+// Built from the last coordinate upwards so that each step is in place:
+//   T[b + size] = T[b] * u_k ;  T[b] = T[b] - T[b + size]
+// ---------------------------------------------------------------------------
+constexpr int BETA_SMALL_MAX = 11;   // one block builds up to 2^11 entries
+
+__global__ __launch_bounds__(ZK_BLOCK) void k_beta_small(const Fr* point, int m, FrTab out) {
+    if (threadIdx.x == 0) tab_st(out, 0, fr_one());
+    __syncthreads();
+    uint64_t size = 1;
+    for (int k = m - 1; k >= 0; --k) {
+        Fr u = point[k];
+        for (uint64_t b = threadIdx.x; b < size; b += blockDim.x) {
+            Fr e = tab_ld(out, b);
+            Fr hi = fr_mul(e, u);
+            tab_st(out, b + size, hi);
+            tab_st(out, b, fr_sub(e, hi));
+        }
+        size <<= 1;
+        __syncthreads();
+    }
+}
+
+// out[(h << lo_bits) | l] = hi[h] * lo[l]
+__global__ __launch_bounds__(ZK_BLOCK) void k_beta_outer(FrTab hi, FrTab lo, int lo_bits, uint64_t n,
+                                                         FrTab out) {
+    uint64_t mask = ((uint64_t)1 << lo_bits) - 1;
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n;
+         i += (uint64_t)gridDim.x * blockDim.x) {
+        Fr a = tab_ld(hi, i >> lo_bits);
+        Fr b = tab_ld(lo, i & mask);
+        tab_st(out, i, fr_mul(a, b));
+    }
+}
+
+int zk_build_beta(zkdl_ctx* ctx, const Fr* point, int m, FrTab out) {
+    if (m <= BETA_SMALL_MAX) {
+        hipLaunchKernelGGL(k_beta_small, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, point, m, out);
+        return ZKDL_OK;
+    }
+    int hb = m / 2, lb = m - hb;
+    uint64_t hn = (uint64_t)1 << hb, ln = (uint64_t)1 << lb;
+    void* tmp = zk_alloc(ctx, (hn + ln) * 32);
+    if (!tmp) return ZKDL_ENOMEM;
+    FrTab th = make_tab(tmp, hn);
+    FrTab tl = make_tab((uint32_t*)tmp + 8 * hn, ln);
+    int rc = zk_build_beta(ctx, point, hb, th);
+    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, point + hb, lb, tl);
+    if (rc == ZKDL_OK) {
+        uint64_t n = (uint64_t)1 << m;
+        hipLaunchKernelGGL(k_beta_outer, dim3(grid_for(n)), dim3(ZK_BLOCK), 0, ctx->stream, th, tl,
+                           lb, n, out);
+    }
+    zk_free(ctx, tmp);   // stream-ordered reuse: later kernels on the same stream run after this one
+    return rc;
+}
+
+// ---------------------------------------------------------------------------
+// partial evaluation: out[o, i] = sum_a beta[a] * T[o, a, i]
+// ---------------------------------------------------------------------------
+template <int KIND>
+__device__ __forceinline__ Fr pe_load(const void* src, uint64_t idx) {
+    if (KIND == TK_FR) {
+        const FrTab* t = (const FrTab*)src;
+        return tab_ld(*t, idx);
+    }
+    return load_src<KIND>(src, idx);
+}
+
+struct PeArgs {
+    const void* src;   // integers, or unused for Fr
+    FrTab fr_src;      // Fr source
+    FrTab beta;
+    FrTab out;         // chunk c of output element e at index c * (O*I) + e
+    uint64_t O, A, I;
+    uint64_t a_chunk;  // contracted-axis entries per chunk
+};
+
+template <int KIND>
+__device__ __forceinline__ Fr pe_elem(const PeArgs& p, uint64_t idx) {
+    if (KIND == TK_FR) return tab_ld(p.fr_src, idx);
+    return load_src<KIND>(p.src, idx);
+}
+
+// one thread per output element (o, i): coalesced when I is large
+template <int KIND>
+__global__ __launch_bounds__(ZK_BLOCK) void k_pe_mid(PeArgs p) {
+    uint64_t n_out = p.O * p.I;
+    uint64_t a0 = (uint64_t)blockIdx.y * p.a_chunk;
+    uint64_t a1 = a0 + p.a_chunk;
+    if (a1 > p.A) a1 = p.A;
+    for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < n_out;
+         e += (uint64_t)gridDim.x * blockDim.x) {
+        uint64_t o = e / p.I, i = e - o * p.I;
+        Fr acc = fr_zero();
+        for (uint64_t a = a0; a < a1; ++a) {
+            Fr x = pe_elem<KIND>(p, (o * p.A + a) * p.I + i);
+            acc = fr_add(acc, fr_mul(tab_ld(p.beta, a), x));
+        }
+        tab_st(p.out, (uint64_t)blockIdx.y * n_out + e, acc);
+    }
+}
+
+__device__ __forceinline__ Fr wave_sum(Fr x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        Fr y;
+#pragma unroll
+        for (int l = 0; l < 8; ++l) y.v[l] = __shfl_down(x.v[l], off, 64);
+        x = fr_add(x, y);
+    }
+    return x;   // lane 0 holds the sum
+}
+
+// innermost axis contracted (I == 1): one wave per (output row, chunk), lanes stride over a
+template <int KIND>
+__global__ __launch_bounds__(ZK_BLOCK) void k_pe_inner(PeArgs p) {
+    const int lane = threadIdx.x & 63;
+    uint64_t wave = (blockIdx.x * (uint64_t)blockDim.x + threadIdx.x) >> 6;
+    uint64_t n_waves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
+    uint64_t chunks = (p.A + p.a_chunk - 1) / p.a_chunk;
+    uint64_t n_items = p.O * chunks;
+    for (uint64_t it = wave; it < n_items; it += n_waves) {
+        uint64_t c = it / p.O, o = it - c * p.O;
+        uint64_t a0 = c * p.a_chunk, a1 = a0 + p.a_chunk;
+        if (a1 > p.A) a1 = p.A;
+        Fr acc = fr_zero();
+        for (uint64_t a = a0 + lane; a < a1; a += 64) {
+            Fr x = pe_elem<KIND>(p, o * p.A + a);
+            acc = fr_add(acc, fr_mul(tab_ld(p.beta, a), x));
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) tab_st(p.out, c * p.O + o, acc);
+    }
+}
+
+// out[e] = sum_c part[c * n + e]
+__global__ __launch_bounds__(ZK_BLOCK) void k_sum_chunks(FrTab part, uint64_t n, uint64_t chunks,
+                                                         FrTab out) {
+    for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < n;
+         e += (uint64_t)gridDim.x * blockDim.x) {
+        Fr acc = tab_ld(part, e);
+        for (uint64_t c = 1; c < chunks; ++c) acc = fr_add(acc, tab_ld(part, c * n + e));
+        tab_st(out, e, acc);
+    }
+}
+
+template <int KIND>
+static void launch_pe(zkdl_ctx* ctx, bool inner, const PeArgs& p, dim3 grid) {
+    if (inner)
+        hipLaunchKernelGGL(k_pe_inner<KIND>, grid, dim3(ZK_BLOCK), 0, ctx->stream, p);
+    else
+        hipLaunchKernelGGL(k_pe_mid<KIND>, grid, dim3(ZK_BLOCK), 0, ctx->stream, p);
+}
+
+int zk_partial_eval(zkdl_ctx* ctx, int kind, const void* src, uint64_t O, uint64_t A, uint64_t I,
+                    FrTab beta, FrTab out) {
+    PeArgs p;
+    p.src = src;
+    if (kind == TK_FR) p.fr_src = *(const FrTab*)src;
+    else p.fr_src = make_tab(nullptr, 0);
+    p.beta = beta;
+    p.O = O;
+    p.A = A;
+    p.I = I;
+    uint64_t n_out = O * I;
+    const bool inner = (I == 1);
+    // split the contracted axis until there is enough parallel work (~64k threads)
+    uint64_t units = inner ? n_out * 64 : n_out;
+    uint64_t chunks = 1;
+    while (units * chunks < 65536 && chunks * 2 <= A && (A / (chunks * 2)) >= (inner ? 64u : 4u)) chunks *= 2;
+    p.a_chunk = (A + chunks - 1) / chunks;
+    void* tmp = nullptr;
+    if (chunks > 1) {
+        tmp = zk_alloc(ctx, chunks * n_out * 32);
+        if (!tmp) return ZKDL_ENOMEM;
+        p.out = make_tab(tmp, chunks * n_out);
+    } else {
+        p.out = out;
+    }
+    dim3 grid;
+    if (inner) {
+        uint64_t waves = n_out * chunks;
+        grid = dim3(grid_for(waves * 64, 16384));
+    } else {
+        grid = dim3(grid_for(n_out, 16384), (unsigned)chunks);
+    }
+    if (kind == TK_FR) launch_pe<TK_FR>(ctx, inner, p, grid);
+    else if (kind == TK_I32) launch_pe<TK_I32>(ctx, inner, p, grid);
+    else launch_pe<TK_I64>(ctx, inner, p, grid);
+    if (chunks > 1) {
+        hipLaunchKernelGGL(k_sum_chunks, dim3(grid_for(n_out)), dim3(ZK_BLOCK), 0, ctx->stream, p.out,
+                           n_out, chunks, out);
+        zk_free(ctx, tmp);
+    }
+    return ZKDL_OK;
+}
+
+// out[r * inner + i] = src[r] : the stack-axis table beta~(w, n) seen over (n, i)
+__global__ __launch_bounds__(ZK_BLOCK) void k_broadcast_rows(FrTab src, uint64_t rows, uint64_t inner,
+                                                             FrTab out) {
+    uint64_t n = rows * inner;
+    for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < n;
+         e += (uint64_t)gridDim.x * blockDim.x)
+        tab_st(out, e, tab_ld(src, e / inner));
+}
+
+void zk_launch_broadcast_rows(zkdl_ctx* ctx, FrTab src, uint64_t rows, uint64_t inner, FrTab out) {
+    hipLaunchKernelGGL(k_broadcast_rows, dim3(grid_for(rows * inner)), dim3(ZK_BLOCK), 0, ctx->stream,
+                       src, rows, inner, out);
+}
+
+// out[r] = src[r + 1] unless r is the last slot of its period, where out[r] = 0:
+// the stack re-indexing "layer l <- layer l+1" of the gradA family
+__global__ __launch_bounds__(ZK_BLOCK) void k_shift_rows(FrTab src, uint64_t rows, uint64_t inner,
+                                                         uint32_t period, FrTab out) {
+    uint64_t n = rows * inner;
+    for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < n;
+         e += (uint64_t)gridDim.x * blockDim.x) {
+        uint64_t r = e / inner;
+        bool last = (r % period) == period - 1;
+        tab_st(out, e, last ? fr_zero() : tab_ld(src, e + inner));
+    }
+}
+
+void zk_launch_shift_rows(zkdl_ctx* ctx, FrTab src, uint64_t rows, uint64_t inner, uint32_t period,
+                          FrTab out) {
+    hipLaunchKernelGGL(k_shift_rows, dim3(grid_for(rows * inner)), dim3(ZK_BLOCK), 0, ctx->stream, src,
+                       rows, inner, period, out);
+}

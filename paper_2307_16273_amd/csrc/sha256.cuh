@@ -1,0 +1,171 @@
+// SHA-256 (FIPS 180-4) and the Fiat-Shamir transcript built on it, usable from
+// host code and from a single GPU thread.
+//
+// The paper's verifier sends a uniform field element after each round
+// polynomial (App. B); the transcript replaces that message by a hash:
+//   state_0          = SHA256("zkdl-mi355x/v1" || u64le(seed))
+//   absorb(label, m) : state <- SHA256(state || u8(|label|) || label || u64le(|m|) || m)
+//   challenge()      : d0 = SHA256(state || 0x00), d1 = SHA256(state || 0x01),
+//                      c = int_le(d0 || d1) mod r, state <- SHA256(state || 0x02)
+#pragma once
+#include <stdint.h>
+#include <hip/hip_runtime.h>
+#include "fr.cuh"
+
+#define SHA_HD __host__ __device__ inline
+
+namespace sha {
+
+SHA_HD uint32_t rotr(uint32_t x, int n) { return (x >> n) | (x << (32 - n)); }
+
+SHA_HD uint32_t kconst(int i) {
+    constexpr uint32_t K[64] = {
+        0x428a2f98, 0x71374491, 0xb5c0fbcf, 0xe9b5dba5, 0x3956c25b, 0x59f111f1, 0x923f82a4, 0xab1c5ed5,
+        0xd807aa98, 0x12835b01, 0x243185be, 0x550c7dc3, 0x72be5d74, 0x80deb1fe, 0x9bdc06a7, 0xc19bf174,
+        0xe49b69c1, 0xefbe4786, 0x0fc19dc6, 0x240ca1cc, 0x2de92c6f, 0x4a7484aa, 0x5cb0a9dc, 0x76f988da,
+        0x983e5152, 0xa831c66d, 0xb00327c8, 0xbf597fc7, 0xc6e00bf3, 0xd5a79147, 0x06ca6351, 0x14292967,
+        0x27b70a85, 0x2e1b2138, 0x4d2c6dfc, 0x53380d13, 0x650a7354, 0x766a0abb, 0x81c2c92e, 0x92722c85,
+        0xa2bfe8a1, 0xa81a664b, 0xc24b8b70, 0xc76c51a3, 0xd192e819, 0xd6990624, 0xf40e3585, 0x106aa070,
+        0x19a4c116, 0x1e376c08, 0x2748774c, 0x34b0bcb5, 0x391c0cb3, 0x4ed8aa4a, 0x5b9cca4f, 0x682e6ff3,
+        0x748f82ee, 0x78a5636f, 0x84c87814, 0x8cc70208, 0x90befffa, 0xa4506ceb, 0xbef9a3f7, 0xc67178f2};
+    return K[i];
+}
+
+// one compression of a 64-byte block given as 16 big-endian words
+SHA_HD void compress(uint32_t h[8], uint32_t w[16]) {
+    uint32_t a = h[0], b = h[1], c = h[2], d = h[3], e = h[4], f = h[5], g = h[6], hh = h[7];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) {
+        if (i >= 16) {
+            uint32_t w15 = w[(i + 1) & 15], w2 = w[(i + 14) & 15];
+            uint32_t s0 = rotr(w15, 7) ^ rotr(w15, 18) ^ (w15 >> 3);
+            uint32_t s1 = rotr(w2, 17) ^ rotr(w2, 19) ^ (w2 >> 10);
+            w[i & 15] = w[i & 15] + s0 + w[(i + 9) & 15] + s1;
+        }
+        uint32_t S1 = rotr(e, 6) ^ rotr(e, 11) ^ rotr(e, 25);
+        uint32_t ch = (e & f) ^ (~e & g);
+        uint32_t t1 = hh + S1 + ch + kconst(i) + w[i & 15];
+        uint32_t S0 = rotr(a, 2) ^ rotr(a, 13) ^ rotr(a, 22);
+        uint32_t mj = (a & b) ^ (a & c) ^ (b & c);
+        uint32_t t2 = S0 + mj;
+        hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + t2;
+    }
+    h[0] += a; h[1] += b; h[2] += c; h[3] += d; h[4] += e; h[5] += f; h[6] += g; h[7] += hh;
+}
+
+// digest of msg[0..len).  The buffer must have room for the padding: its
+// capacity must be at least ((len + 9 + 63) / 64) * 64 bytes; it is overwritten.
+SHA_HD void digest_inplace(uint8_t* msg, uint32_t len, uint8_t out[32]) {
+    uint32_t total = ((len + 9 + 63) / 64) * 64;
+    msg[len] = 0x80;
+    for (uint32_t i = len + 1; i < total - 8; ++i) msg[i] = 0;
+    uint64_t bits = (uint64_t)len * 8;
+    for (int i = 0; i < 8; ++i) msg[total - 1 - i] = (uint8_t)(bits >> (8 * i));
+    uint32_t h[8] = {0x6a09e667, 0xbb67ae85, 0x3c6ef372, 0xa54ff53a,
+                     0x510e527f, 0x9b05688c, 0x1f83d9ab, 0x5be0cd19};
+    for (uint32_t off = 0; off < total; off += 64) {
+        uint32_t w[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint8_t* p = msg + off + 4 * i;
+            w[i] = ((uint32_t)p[0] << 24) | ((uint32_t)p[1] << 16) | ((uint32_t)p[2] << 8) | p[3];
+        }
+        compress(h, w);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        out[4 * i] = (uint8_t)(h[i] >> 24);
+        out[4 * i + 1] = (uint8_t)(h[i] >> 16);
+        out[4 * i + 2] = (uint8_t)(h[i] >> 8);
+        out[4 * i + 3] = (uint8_t)h[i];
+    }
+}
+
+// SHA256(state || suffix) for a one-byte suffix, from registers only
+SHA_HD void digest_state_suffix(const uint8_t state[32], uint8_t suffix, uint8_t out[32]) {
+    uint32_t w[16];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        w[i] = ((uint32_t)state[4 * i] << 24) | ((uint32_t)state[4 * i + 1] << 16) |
+               ((uint32_t)state[4 * i + 2] << 8) | state[4 * i + 3];
+    w[8] = ((uint32_t)suffix << 24) | 0x00800000u;
+#pragma unroll
+    for (int i = 9; i < 15; ++i) w[i] = 0;
+    w[15] = 33 * 8;
+    uint32_t h[8] = {0x6a09e667, 0xbb67ae85, 0x3c6ef372, 0xa54ff53a,
+                     0x510e527f, 0x9b05688c, 0x1f83d9ab, 0x5be0cd19};
+    compress(h, w);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        out[4 * i] = (uint8_t)(h[i] >> 24);
+        out[4 * i + 1] = (uint8_t)(h[i] >> 16);
+        out[4 * i + 2] = (uint8_t)(h[i] >> 8);
+        out[4 * i + 3] = (uint8_t)h[i];
+    }
+}
+
+}  // namespace sha
+
+namespace ts {
+
+constexpr uint32_t MAX_LABEL = 32;
+// scratch needed by absorb() for `n` data bytes
+SHA_HD uint32_t scratch_bytes(uint32_t n) { return ((32 + 1 + MAX_LABEL + 8 + n + 9 + 63) / 64) * 64; }
+
+// state <- SHA256(state || u8(label_len) || label || u64le(n) || data); `buf` is
+// scratch of at least scratch_bytes(n) bytes (LDS on the device)
+SHA_HD void absorb(uint8_t state[32], const char* label, uint32_t label_len, const uint8_t* data,
+                   uint32_t n, uint8_t* buf) {
+    uint32_t p = 0;
+    for (int i = 0; i < 32; ++i) buf[p++] = state[i];
+    buf[p++] = (uint8_t)label_len;
+    for (uint32_t i = 0; i < label_len; ++i) buf[p++] = (uint8_t)label[i];
+    uint64_t n64 = n;
+    for (int i = 0; i < 8; ++i) buf[p++] = (uint8_t)(n64 >> (8 * i));
+    for (uint32_t i = 0; i < n; ++i) buf[p++] = data[i];
+    sha::digest_inplace(buf, p, state);
+}
+
+// draw one challenge; returns it in Montgomery form and, if le_out != nullptr,
+// as 32 canonical little-endian bytes
+SHA_HD Fr challenge(uint8_t state[32], uint8_t* le_out) {
+    uint8_t d0[32], d1[32], nx[32];
+    sha::digest_state_suffix(state, 0x00, d0);
+    sha::digest_state_suffix(state, 0x01, d1);
+    sha::digest_state_suffix(state, 0x02, nx);
+    Fr lo, hi;
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+        lo.v[l] = d0[4 * l] | ((uint32_t)d0[4 * l + 1] << 8) | ((uint32_t)d0[4 * l + 2] << 16) |
+                  ((uint32_t)d0[4 * l + 3] << 24);
+        hi.v[l] = d1[4 * l] | ((uint32_t)d1[4 * l + 1] << 8) | ((uint32_t)d1[4 * l + 2] << 16) |
+                  ((uint32_t)d1[4 * l + 3] << 24);
+    }
+    for (int i = 0; i < 32; ++i) state[i] = nx[i];
+    Fr c = fr_from_wide(lo, hi);
+    if (le_out) {
+        Fr plain = fr_from_mont(c);
+#pragma unroll
+        for (int l = 0; l < 8; ++l) {
+            le_out[4 * l] = (uint8_t)plain.v[l];
+            le_out[4 * l + 1] = (uint8_t)(plain.v[l] >> 8);
+            le_out[4 * l + 2] = (uint8_t)(plain.v[l] >> 16);
+            le_out[4 * l + 3] = (uint8_t)(plain.v[l] >> 24);
+        }
+    }
+    return c;
+}
+
+// canonical little-endian bytes of a Montgomery-form element
+SHA_HD void fr_to_le(const Fr& mont, uint8_t out[32]) {
+    Fr plain = fr_from_mont(mont);
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+        out[4 * l] = (uint8_t)plain.v[l];
+        out[4 * l + 1] = (uint8_t)(plain.v[l] >> 8);
+        out[4 * l + 2] = (uint8_t)(plain.v[l] >> 16);
+        out[4 * l + 3] = (uint8_t)(plain.v[l] >> 24);
+    }
+}
+
+}  // namespace ts

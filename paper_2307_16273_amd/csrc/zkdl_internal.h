@@ -1,0 +1,119 @@
+// Internal declarations shared by the translation units of the library.
+#pragma once
+#include <stdint.h>
+#include <stddef.h>
+#include <map>
+#include <vector>
+#include <hip/hip_runtime.h>
+
+#include "fr.cuh"
+#include "sha256.cuh"
+#include "../../include/zkdl.h"
+
+constexpr int ZK_MAX_CHAL = 1024;          // challenges one call may draw
+constexpr int ZK_PROOF_CAP = 1 << 17;      // proof bytes one call may write
+constexpr int ZK_MAX_PART_BLOCKS = 2048;   // partial-sum slots of a round kernel
+constexpr int ZK_MAX_EVALS = 4;            // evaluations per round polynomial (degree <= 3)
+constexpr int ZK_BLOCK = 256;
+
+// Device-resident state of the call in flight.
+struct DevState {
+    uint8_t ts_state[32];   // transcript state
+    uint32_t err;           // bit 0: zkReLU input out of range
+    uint32_t pad0[7];
+    Fr claim;               // claim of the running sumcheck (Montgomery)
+    Fr inv2, inv6;          // constants of the Lagrange formulas
+    Fr weights[8];          // zkReLU: r^2, r, r'r^2, r'r, r'
+    Fr scal[64];            // scalars handed between kernels (claims, finals)
+    Fr chal[ZK_MAX_CHAL];   // challenges, Montgomery form
+    uint8_t chal_le[ZK_MAX_CHAL * 32];
+    uint8_t proof[ZK_PROOF_CAP];
+};
+
+enum TensorKind { TK_FR = 0, TK_I32 = 1, TK_I64 = 2 };
+
+struct zkdl_tensor {
+    int kind;
+    int ndim;
+    uint64_t shape[ZKDL_MAX_DIMS];
+    uint64_t numel;
+    void* data;      // TK_FR: uint32_t planes (8 * numel words); else the integers
+    bool owned;
+};
+
+struct zkdl_transcript {
+    uint8_t state[32];
+};
+
+struct zkdl_ctx {
+    int device;
+    hipStream_t stream;
+    int last_hip;
+    DevState* dev;            // device
+    uint8_t* host_stage;      // pinned host staging (sizeof(DevState))
+    Fr* partials;             // device: ZK_MAX_PART_BLOCKS * ZK_MAX_EVALS * 2 partial sums
+    std::multimap<size_t, void*> free_blocks;
+    std::map<void*, size_t> live_blocks;
+    // per-call bookkeeping (host mirrors of device cursors)
+    int n_chal;
+    size_t proof_len;
+};
+
+#define ZK_HIP(ctx, call)                       \
+    do {                                        \
+        hipError_t e__ = (call);                \
+        if (e__ != hipSuccess) {                \
+            (ctx)->last_hip = (int)e__;         \
+            return ZKDL_EHIP;                   \
+        }                                       \
+    } while (0)
+
+// scratch allocator of the context (caches freed blocks)
+void* zk_alloc(zkdl_ctx* ctx, size_t bytes);
+void zk_free(zkdl_ctx* ctx, void* p);
+
+static inline FrTab make_tab(void* p, uint64_t ps) {
+    FrTab t;
+    t.p = (uint32_t*)p;
+    t.ps = ps;
+    return t;
+}
+static inline FrTab tab_offset(const FrTab& t, uint64_t elems) {
+    FrTab o = t;
+    o.p += elems;
+    return o;
+}
+
+// ---- k_basic.hip -------------------------------------------------------------
+void zk_launch_convert(zkdl_ctx* ctx, const void* src, int kind_or_le, uint64_t n, FrTab out);
+void zk_launch_download(zkdl_ctx* ctx, FrTab in, uint64_t n, uint8_t* out_le_dev);
+void zk_launch_points_to_mont(zkdl_ctx* ctx, const uint8_t* le_dev, int n, Fr* out);
+// beta~(point, .) for the m challenges point[0..m) (device, Montgomery, AoS)
+int zk_build_beta(zkdl_ctx* ctx, const Fr* point, int m, FrTab out);
+// out[o, i] = sum_a beta[a] * src[o, a, i]; src kind TK_*; out has O * I elements
+int zk_partial_eval(zkdl_ctx* ctx, int kind, const void* src, uint64_t O, uint64_t A, uint64_t I,
+                    FrTab beta, FrTab out);
+void zk_launch_broadcast_rows(zkdl_ctx* ctx, FrTab src, uint64_t rows, uint64_t inner, FrTab out);
+void zk_launch_shift_rows(zkdl_ctx* ctx, FrTab src, uint64_t rows, uint64_t inner, uint32_t period,
+                          FrTab out);
+
+// ---- k_sumcheck.hip ------------------------------------------------------------
+struct ScTables {
+    FrTab src[3];
+    FrTab dst[3];
+};
+// Runs all rounds of a degree-K product sumcheck on K tables of length 2^d.
+// src tables are read only; work tables (length 2^(d-1) each, if d >= 1) receive
+// the folded values.  Writes one SC block at ctx->proof_len, draws d challenges.
+int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, const FrTab* work, int d,
+                        int finals_scal_base);
+void zk_launch_draw(zkdl_ctx* ctx, int chal_base, int count);
+void zk_launch_absorb_scal(zkdl_ctx* ctx, const char* label, int scal_base, int count,
+                           size_t proof_off);
+
+// ---- k_zkrelu.hip ----------------------------------------------------------------
+int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q, int R);
+
+// ---- api.hip -----------------------------------------------------------------------
+void zk_write_proof_words(zkdl_ctx* ctx, const uint32_t* words, int n);   // appends a header
+void zk_host_absorb_u32(zkdl_transcript* t, const char* label, const uint32_t* words, int n);

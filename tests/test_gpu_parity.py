@@ -1,0 +1,184 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI.
+
+Bit-exact on every proof byte, challenge, claim and the final transcript state.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle.field import R_MOD, fr_array, fr_array_from_le, array_to_le
+from oracle.mle import partial_eval
+from oracle import protocols as P
+from oracle.transcript import Transcript as OracleTranscript
+from workloads import uniform_fr_limbs, fcnn_window, fc_relu_layer, CONFIG_SEED
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    c = lib.Context(0)
+    yield c
+    c.close()
+
+
+def rand_fr_bytes(seed, n):
+    return uniform_fr_limbs(np.random.default_rng(seed), n).tobytes()
+
+
+@pytest.mark.parametrize("dtype", ["i32", "i64", "fr"])
+def test_upload_download_roundtrip(lib, ctx, dtype):
+    say(f"upload/download {dtype}")
+    rng = np.random.default_rng(3)
+    n = 1 << 10
+    if dtype == "i32":
+        src = rng.integers(-2 ** 31, 2 ** 31, n, dtype=np.int64).astype(np.int32)
+        src[:4] = [0, -1, 2 ** 31 - 1, -2 ** 31]
+        expect = fr_array(src)
+    elif dtype == "i64":
+        src = rng.integers(-2 ** 63, 2 ** 63, n, dtype=np.int64)
+        src[:4] = [0, -1, 2 ** 63 - 1, -2 ** 63]
+        expect = fr_array(src)
+    else:
+        limbs = uniform_fr_limbs(rng, n)
+        limbs[0] = 0
+        limbs[1] = [0xFFFFFFFF00000000, 0x53BDA402FFFE5BFE, 0x3339D80809A1D805, 0x73EDA753299D7D48]  # r - 1
+        src = limbs.tobytes()
+        expect = fr_array_from_le(src, n)
+    t = lib.fr_tensor_upload(ctx, src, (n,))
+    assert t.shape == (n,)
+    assert t.download() == array_to_le(expect)
+
+
+def test_upload_from_device_memory(lib, ctx):
+    import torch
+    say("upload from device")
+    src = np.random.default_rng(4).integers(-2 ** 31, 2 ** 31, 4096, dtype=np.int64).astype(np.int32)
+    t = lib.fr_tensor_upload(ctx, torch.from_numpy(src).cuda(), (64, 64))
+    assert t.download() == array_to_le(fr_array(src))
+    w = lib.tensor_wrap_int(ctx, torch.from_numpy(src).cuda().reshape(64, 64))
+    assert w.download() == array_to_le(fr_array(src))
+
+
+PE_CASES = [
+    ((8, 16, 32), 0, 1, "fr"), ((8, 16, 32), 1, 2, "fr"), ((8, 16, 32), 2, 3, "fr"),
+    ((8, 16, 32), 0, 3, "fr"), ((8, 16, 32), 1, 3, "i32"), ((4, 64, 2), 1, 2, "i64"),
+    ((1, 1, 1), 0, 3, "fr"), ((2048, 64), 0, 1, "fr"), ((64, 4096), 1, 2, "i32"),
+    ((16384,), 0, 1, "fr"), ((2, 8192, 2), 1, 2, "i32"),
+]
+
+
+@pytest.mark.parametrize("shape,lo,hi,kind", PE_CASES)
+def test_mle_partial_eval(lib, ctx, shape, lo, hi, kind):
+    say(f"partial_eval shape={shape} axes=[{lo},{hi}) {kind}")
+    rng = np.random.default_rng(hash((shape, lo, hi)) % 2 ** 32)
+    n = int(np.prod(shape))
+    if kind == "fr":
+        raw = uniform_fr_limbs(rng, n).tobytes()
+        ref = fr_array_from_le(raw, n)
+        t = lib.fr_tensor_upload(ctx, raw, shape)
+    elif kind == "i32":
+        import torch
+        src = rng.integers(-2 ** 31, 2 ** 31, n, dtype=np.int64).astype(np.int32)
+        ref = fr_array(src)
+        t = lib.tensor_wrap_int(ctx, torch.from_numpy(src).cuda(), shape)
+    else:
+        import torch
+        src = rng.integers(-2 ** 47, 2 ** 47, n, dtype=np.int64)
+        ref = fr_array(src)
+        t = lib.tensor_wrap_int(ctx, torch.from_numpy(src).cuda(), shape)
+    npt = sum(int(s).bit_length() - 1 for s in shape[lo:hi])
+    point = fr_array_from_le(rand_fr_bytes(99, max(npt, 1)), max(npt, 1)).tolist()[:npt]
+    out = lib.mle_partial_eval(ctx, t, lo, hi, point)
+    expect, oshape = partial_eval(ref, shape, lo, hi, point)
+    assert list(out.shape) == oshape
+    assert out.download() == array_to_le(expect)
+
+
+@pytest.mark.parametrize("k,d", [(3, 0), (3, 1), (3, 2), (1, 5), (2, 9), (3, 10), (3, 14)])
+def test_sumcheck_product(lib, ctx, k, d):
+    say(f"sumcheck_product K={k} d={d}")
+    n = 1 << d
+    raws = [rand_fr_bytes(1000 + 10 * d + j, n) for j in range(k)]
+    tabs = [lib.fr_tensor_upload(ctx, r, (n,)) for r in raws]
+    tr = lib.Transcript(77)
+    got = lib.sumcheck_product(ctx, tabs, tr)
+    ots = OracleTranscript(77)
+    buf, proof, vs = P.product_prove([fr_array_from_le(r, n) for r in raws], ots)
+    assert got["proof"] == buf
+    assert got["points"] == ots.challenges
+    assert got["claims"] == proof.finals
+    assert tr.digest() == ots.digest()
+    # inputs are untouched
+    assert tabs[0].download() == raws[0]
+
+
+@pytest.mark.parametrize("n,d1,d2,d3,t0,t1,kind", [
+    (1, 16, 256, 256, False, False, "i32"),      # one FC layer, batch 16 (config 1 shape)
+    (4, 8, 32, 16, False, False, "fr"),
+    (4, 8, 32, 16, True, False, "i32"),
+    (4, 8, 32, 16, False, True, "i32"),
+    (2, 1, 2, 1, False, False, "fr"),
+    (8, 4, 64, 64, True, True, "i32"),
+])
+def test_sumcheck_matmul(lib, ctx, n, d1, d2, d3, t0, t1, kind):
+    import torch
+    say(f"sumcheck_matmul N={n} D=({d1},{d2},{d3}) tr=({t0},{t1}) {kind}")
+    rng = np.random.default_rng(n * 1000 + d1 + d2 + d3)
+    x0 = rng.integers(-2 ** 31, 2 ** 31, (n, d1, d2), dtype=np.int64).astype(np.int32)
+    x1 = rng.integers(-2 ** 31, 2 ** 31, (n, d2, d3), dtype=np.int64).astype(np.int32)
+    s0 = np.ascontiguousarray(np.transpose(x0, (0, 2, 1))) if t0 else x0     # what is stored
+    s1 = np.ascontiguousarray(np.transpose(x1, (0, 2, 1))) if t1 else x1
+    if kind == "i32":
+        a = lib.tensor_wrap_int(ctx, torch.from_numpy(s0).cuda())
+        b = lib.tensor_wrap_int(ctx, torch.from_numpy(s1).cuda())
+    else:
+        a = lib.fr_tensor_upload(ctx, s0, s0.shape)
+        b = lib.fr_tensor_upload(ctx, s1, s1.shape)
+    tr = lib.Transcript(5)
+    got = lib.sumcheck_matmul(ctx, a, b, tr, t0, t1)
+    ots = OracleTranscript(5)
+    buf, proof, pts = P.matmul_prove(fr_array(x0), [n, d1, d2], fr_array(x1), [n, d2, d3], ots)
+    assert got["proof"] == buf
+    assert got["points"] == ots.challenges
+    assert got["claims"] == [proof.claim0, proof.finals[1], proof.finals[2]]
+    assert tr.digest() == ots.digest()
+
+
+@pytest.mark.parametrize("shape", [(1,), (2, 4, 4), (4, 64, 16)])
+def test_sumcheck_hadamard(lib, ctx, shape):
+    say(f"sumcheck_hadamard shape={shape}")
+    rng = np.random.default_rng(17)
+    x0 = rng.integers(-2 ** 31, 2 ** 31, shape, dtype=np.int64).astype(np.int32)
+    x1 = rng.integers(-2 ** 31, 2 ** 31, shape, dtype=np.int64).astype(np.int32)
+    a = lib.fr_tensor_upload(ctx, x0, shape)
+    b = lib.fr_tensor_upload(ctx, x1, shape)
+    tr = lib.Transcript(6)
+    got = lib.sumcheck_hadamard(ctx, a, b, tr)
+    ots = OracleTranscript(6)
+    buf, proof, pts = P.hadamard_prove(fr_array(x0), fr_array(x1), ots)
+    assert got["proof"] == buf and got["points"] == ots.challenges
+    assert got["claims"] == [proof.claim0, proof.finals[1], proof.finals[2]]
+    assert tr.digest() == ots.digest()
+
+
+def test_chained_calls_share_one_transcript(lib, ctx):
+    say("chained calls")
+    n = 64
+    raws = [rand_fr_bytes(50 + j, n) for j in range(2)]
+    tabs = [lib.fr_tensor_upload(ctx, r, (n,)) for r in raws]
+    tr = lib.Transcript(1)
+    tr.absorb(b"digest", b"\x07" * 32)
+    g1 = lib.sumcheck_product(ctx, tabs, tr)
+    g2 = lib.sumcheck_product(ctx, tabs[:1], tr)
+    ots = OracleTranscript(1)
+    ots.absorb(b"digest", b"\x07" * 32)
+    b1, _, _ = P.product_prove([fr_array_from_le(r, n) for r in raws], ots)
+    b2, _, _ = P.product_prove([fr_array_from_le(raws[0], n)], ots)
+    assert g1["proof"] == b1 and g2["proof"] == b2 and tr.digest() == ots.digest()
