@@ -86,3 +86,17 @@ __device__ inline Fr dev_challenge(DevState* st, int idx) {
     for (int i = 0; i < 32; ++i) st->chal_le[32 * idx + i] = le[i];
     return c;
 }
+
+// thread-0 step that closes a round: g_t(0..npts-1) go to the proof and into the
+// transcript, the round's challenge is drawn, the next claim is g_t(v_t).
+__device__ inline Fr dev_finalise_round(DevState* st, const Fr* g, int npts, uint32_t proof_off,
+                                        int chal_idx, uint8_t* lds) {
+    dev_absorb_frs(st, "g", 1, g, npts, st->proof + proof_off, lds);
+    Fr v = dev_challenge(st, chal_idx);
+    st->claim = lagrange_at(g, npts, v, st->inv2, st->inv6);
+    return v;
+}
+
+// ---- launchers defined in k_sumcheck.hip ----
+void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_t proof_off, int first,
+                        uint32_t claim_off);

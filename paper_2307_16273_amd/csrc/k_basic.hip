@@ -309,3 +309,13 @@ void zk_launch_shift_rows(zkdl_ctx* ctx, FrTab src, uint64_t rows, uint64_t inne
     hipLaunchKernelGGL(k_shift_rows, dim3(grid_for(rows * inner)), dim3(ZK_BLOCK), 0, ctx->stream, src,
                        rows, inner, period, out);
 }
+
+// small SoA table -> array of structures (tables that single-block kernels index directly)
+__global__ void k_soa_to_aos(FrTab in, int n, Fr* out) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = tab_ld(in, i);
+}
+
+void zk_launch_soa_to_aos(zkdl_ctx* ctx, FrTab in, int n, Fr* out) {
+    hipLaunchKernelGGL(k_soa_to_aos, dim3((n + 63) / 64), dim3(64), 0, ctx->stream, in, n, out);
+}

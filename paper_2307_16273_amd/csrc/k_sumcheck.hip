@@ -93,10 +93,22 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_finalise(FinArgs a) {
             Fr c0 = fr_add(g[0], g[1]);
             dev_absorb_frs(st, "c", 1, &c0, 1, st->proof + a.claim_off, lds);
         }
-        dev_absorb_frs(st, "g", 1, g, a.npts, st->proof + a.proof_off, lds);
-        Fr v = dev_challenge(st, a.chal_idx);
-        st->claim = lagrange_at(g, a.npts, v, st->inv2, st->inv6);
+        dev_finalise_round(st, g, a.npts, a.proof_off, a.chal_idx, lds);
     }
+}
+
+void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_t proof_off, int first,
+                        uint32_t claim_off) {
+    FinArgs fa;
+    fa.part = ctx->partials;
+    fa.nblk = nblk;
+    fa.npts = npts;
+    fa.st = ctx->dev;
+    fa.chal_idx = chal_idx;
+    fa.proof_off = proof_off;
+    fa.first = first;
+    fa.claim_off = claim_off;
+    hipLaunchKernelGGL(k_sc_finalise, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, fa);
 }
 
 struct FinishArgs {
@@ -174,16 +186,8 @@ int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, const FrTab* wor
         if (K == 1) launch_round<1>(ctx, fold, ra, grid);
         else if (K == 2) launch_round<2>(ctx, fold, ra, grid);
         else launch_round<3>(ctx, fold, ra, grid);
-        FinArgs fa;
-        fa.part = ctx->partials;
-        fa.nblk = (int)grid;
-        fa.npts = npts;
-        fa.st = ctx->dev;
-        fa.chal_idx = ctx->n_chal++;
-        fa.proof_off = rounds_off + (uint32_t)t * npts * 32;
-        fa.first = (t == 0);
-        fa.claim_off = claim_off;
-        hipLaunchKernelGGL(k_sc_finalise, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+        zk_launch_finalise(ctx, (int)grid, npts, ctx->n_chal++, rounds_off + (uint32_t)t * npts * 32,
+                           t == 0, claim_off);
     }
     FinishArgs fi;
     const FrTab* from = (d <= 1) ? src : work;

@@ -1,4 +1,798 @@
+// zkReLU (Sec. 3.1, App. A): the combined sumcheck of the six equations
+//   forward in / out / binarity, backward in / out / binarity
+// with weights r^2, r, 1, r'r^2, r'r, r', over aux in {0,1}^{2 x D x J}
+// (J = Q+R padded to a power of two), followed by the merge of the three claims
+// on aux into one.
+//
+// How the sum is organised here (same field elements as the direct double sum
+// over (i, j), grouped differently):
+//  * The "in" and "out" equations are linear in aux along j, and
+//    sum_j aux(k,i,j) s(j) is the integer itself (Eqs. aux-Z, aux-GA) while
+//    sum_j aux(k,i,j) s'(j) is the rescaled integer.  Folding over i commutes with
+//    these sums, so during the i-rounds they run on D-sized tables
+//    (k_zk_lin): beta*Z, beta*(1-sign)*Z', beta*G_A, beta*(1-sign)*G_A'.
+//  * Only the binarity terms need the D x (Q+R) tables (k_zk_bin*).  Their
+//    equality factor splits as beta~(u_bin,(i,j)) = beta_I(i) beta_J(j).
+//    Round 0 works on the integers directly: aux is binary, so
+//    a(x)^2 - a(x) = (x^2 - x) [bit_lo != bit_hi].  After the first challenge the
+//    tables are field elements from {0, 1, v, 1-v} and are written out once
+//    (k_zk_mat), column-major: entry (k, j, i) at plane (k*(Q+R)+j), so that
+//    threads over i read coalesced limb planes.
+//  * The j-rounds (log2 J of them) and the merge run on 64/128-entry tables in a
+//    single block (k_zk_tail) together with their transcript steps.
 #include "dev_common.cuh"
+
+namespace {
+
+constexpr int LIN_TABLES = 10;
+// order of the D-sized tables
+enum { T_BZ = 0, T_Z, T_BA, T_NS, T_ZP, T_BGA, T_GA, T_BGZ, T_GAP, T_BI };
+
+struct ZkTabs {
+    FrTab t[LIN_TABLES];
+};
+
+__device__ __forceinline__ int64_t rescale_half_up(int64_t x, int r_bits) {
+    // floor((x + 2^(R-1)) / 2^R) without overflow
+    return ((x >> (r_bits - 1)) + 1) >> 1;
+}
+
+__device__ __forceinline__ bool in_range(int64_t x, int nbits) {
+    if (nbits >= 64) return true;
+    int64_t top = x >> (nbits - 1);
+    return top == 0 || top == -1;
+}
+
+// ---------------------------------------------------------------------------
+// prepare: the D-sized value tables and the four input claims
+// ---------------------------------------------------------------------------
+struct PrepArgs {
+    const int64_t* z;
+    const int64_t* ga;   // nullptr: G_A = 0
+    uint64_t D;
+    int nbits, r_bits;
+    ZkTabs tabs;         // beta tables are read, value tables written
+    Fr* part;            // per block: 4 partial dot products
+    DevState* st;
+};
+
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_prepare(PrepArgs a) {
+    __shared__ uint32_t red[64];
+    Fr acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = fr_zero();
+    bool bad = false;
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < a.D;
+         i += (uint64_t)gridDim.x * blockDim.x) {
+        int64_t z = a.z[i];
+        bad |= !in_range(z, a.nbits);
+        bool neg = (z >> (a.nbits - 1)) & 1;            // aux(0, i, Q+R-1)
+        int64_t zp = rescale_half_up(z, a.r_bits);
+        Fr fz = fr_from_i64(z), fzp = fr_from_i64(zp);
+        tab_st(a.tabs.t[T_Z], i, fz);
+        tab_st(a.tabs.t[T_ZP], i, fzp);
+        tab_st(a.tabs.t[T_NS], i, neg ? fr_zero() : fr_one());
+        acc[0] = fr_add(acc[0], fr_mul(tab_ld(a.tabs.t[T_BZ], i), fz));
+        if (!neg) acc[1] = fr_add(acc[1], fr_mul(tab_ld(a.tabs.t[T_BA], i), fzp));
+        if (a.ga) {
+            int64_t g = a.ga[i];
+            bad |= !in_range(g, a.nbits);
+            int64_t gp = rescale_half_up(g, a.r_bits);
+            Fr fg = fr_from_i64(g), fgp = fr_from_i64(gp);
+            tab_st(a.tabs.t[T_GA], i, fg);
+            tab_st(a.tabs.t[T_GAP], i, fgp);
+            acc[2] = fr_add(acc[2], fr_mul(tab_ld(a.tabs.t[T_BGA], i), fg));
+            if (!neg) acc[3] = fr_add(acc[3], fr_mul(tab_ld(a.tabs.t[T_BGZ], i), fgp));
+        }
+    }
+    if (bad) atomicOr(&a.st->err, 1u);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        Fr s = block_sum(acc[q], red);
+        if (threadIdx.x == 0) a.part[(uint64_t)blockIdx.x * 4 + q] = s;
+    }
+}
+
+struct ClaimsArgs {
+    const Fr* part;
+    int nblk;
+    DevState* st;
+    uint32_t claims_off;   // four input claims
+    uint32_t claim0_off;   // claim_0 of the combined sumcheck
+    int chal_r;            // index of r; r' follows
+};
+
+// input claims -> proof and transcript; draw r, r'; weights; combined claim
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_claims(ClaimsArgs a) {
+    __shared__ uint32_t red[64];
+    __shared__ uint8_t lds[TS_LDS_BYTES];
+    __shared__ Fr c[4];
+    for (int q = 0; q < 4; ++q) {
+        Fr s = fr_zero();
+        for (int b = threadIdx.x; b < a.nblk; b += blockDim.x) s = fr_add(s, a.part[(uint64_t)b * 4 + q]);
+        s = block_sum(s, red);
+        if (threadIdx.x == 0) c[q] = s;
+    }
+    if (threadIdx.x != 0) return;
+    DevState* st = a.st;
+    for (int q = 0; q < 4; ++q) st->scal[q] = c[q];
+    dev_absorb_frs(st, "c", 1, c, 4, st->proof + a.claims_off, lds);
+    Fr r = dev_challenge(st, a.chal_r);
+    Fr rp = dev_challenge(st, a.chal_r + 1);
+    Fr r2 = fr_sqr(r);
+    st->weights[0] = r2;
+    st->weights[1] = r;
+    st->weights[2] = fr_mul(rp, r2);
+    st->weights[3] = fr_mul(rp, r);
+    st->weights[4] = rp;
+    Fr claim = fr_zero();
+    for (int q = 0; q < 4; ++q) claim = fr_add(claim, fr_mul(st->weights[q], c[q]));
+    st->claim = claim;
+    ts::fr_to_le(claim, st->proof + a.claim0_off);
+}
+
+// the equation weights go into the four beta tables: beta_Z *= r^2, beta_A *= r, ...
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_scale(ZkTabs tabs, uint64_t D, const Fr* weights, int has_ga) {
+    Fr w0 = weights[0], w1 = weights[1], w2 = weights[2], w3 = weights[3];
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < D;
+         i += (uint64_t)gridDim.x * blockDim.x) {
+        tab_st(tabs.t[T_BZ], i, fr_mul(tab_ld(tabs.t[T_BZ], i), w0));
+        tab_st(tabs.t[T_BA], i, fr_mul(tab_ld(tabs.t[T_BA], i), w1));
+        if (has_ga) {
+            tab_st(tabs.t[T_BGA], i, fr_mul(tab_ld(tabs.t[T_BGA], i), w2));
+            tab_st(tabs.t[T_BGZ], i, fr_mul(tab_ld(tabs.t[T_BGZ], i), w3));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// i-rounds, linear equations on the D-sized tables
+// ---------------------------------------------------------------------------
+struct LinArgs {
+    ZkTabs tabs;
+    uint64_t m;
+    const Fr* chal;
+    Fr* part;
+    int has_ga;
+};
+
+template <bool FOLD>
+__device__ __forceinline__ void lin_pair(const FrTab& t, uint64_t b, uint64_t m, const Fr& v, Fr& lo, Fr& hi) {
+    if (FOLD) {
+        Fr t0 = tab_ld(t, b), t1 = tab_ld(t, b + m), t2 = tab_ld(t, b + 2 * m), t3 = tab_ld(t, b + 3 * m);
+        lo = fr_add(t0, fr_mul(v, fr_sub(t2, t0)));
+        hi = fr_add(t1, fr_mul(v, fr_sub(t3, t1)));
+        tab_st(t, b, lo);
+        tab_st(t, b + m, hi);
+    } else {
+        lo = tab_ld(t, b);
+        hi = tab_ld(t, b + m);
+    }
+}
+
+// values of lo + x (hi - lo) at x = 0..3
+__device__ __forceinline__ void line4(const Fr& lo, const Fr& hi, Fr e[4]) {
+    Fr d = fr_sub(hi, lo);
+    e[0] = lo;
+    e[1] = hi;
+    e[2] = fr_add(hi, d);
+    e[3] = fr_add(e[2], d);
+}
+
+template <bool FOLD>
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_lin(LinArgs a) {
+    __shared__ uint32_t red[64];
+    Fr acc[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) acc[x] = fr_zero();
+    Fr v = fr_zero();
+    if (FOLD) v = *a.chal;
+    const uint64_t m = a.m;
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
+         b += (uint64_t)gridDim.x * blockDim.x) {
+        Fr lo, hi, ns[4], p[4], q[4];
+        lin_pair<FOLD>(a.tabs.t[T_NS], b, m, v, lo, hi);
+        line4(lo, hi, ns);
+        // the equality table of the binarity terms is only carried along here
+        lin_pair<FOLD>(a.tabs.t[T_BI], b, m, v, lo, hi);
+        // r^2 beta_Z * Z
+        lin_pair<FOLD>(a.tabs.t[T_BZ], b, m, v, lo, hi);
+        line4(lo, hi, p);
+        lin_pair<FOLD>(a.tabs.t[T_Z], b, m, v, lo, hi);
+        line4(lo, hi, q);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) acc[x] = fr_add(acc[x], fr_mul(p[x], q[x]));
+        // r beta_A * (1 - sign) * Z'
+        lin_pair<FOLD>(a.tabs.t[T_BA], b, m, v, lo, hi);
+        line4(lo, hi, p);
+        lin_pair<FOLD>(a.tabs.t[T_ZP], b, m, v, lo, hi);
+        line4(lo, hi, q);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) acc[x] = fr_add(acc[x], fr_mul(fr_mul(p[x], ns[x]), q[x]));
+        if (a.has_ga) {
+            // r' r^2 beta_GA * G_A
+            lin_pair<FOLD>(a.tabs.t[T_BGA], b, m, v, lo, hi);
+            line4(lo, hi, p);
+            lin_pair<FOLD>(a.tabs.t[T_GA], b, m, v, lo, hi);
+            line4(lo, hi, q);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) acc[x] = fr_add(acc[x], fr_mul(p[x], q[x]));
+            // r' r beta_GZ * (1 - sign) * G_A'
+            lin_pair<FOLD>(a.tabs.t[T_BGZ], b, m, v, lo, hi);
+            line4(lo, hi, p);
+            lin_pair<FOLD>(a.tabs.t[T_GAP], b, m, v, lo, hi);
+            line4(lo, hi, q);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) acc[x] = fr_add(acc[x], fr_mul(fr_mul(p[x], ns[x]), q[x]));
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        Fr s = block_sum(acc[x], red);
+        if (threadIdx.x == 0) a.part[(uint64_t)blockIdx.x * 4 + x] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// i-rounds, binarity terms
+// ---------------------------------------------------------------------------
+struct BinArgs {
+    const int64_t* z;      // round 0 / materialise only
+    const int64_t* ga;
+    uint32_t* aux;         // Fr planes: entry (k, j, i) = limb planes at ((k*nbits + j)*8 + l)*ps + i
+    uint64_t ps;
+    int nbits;
+    int has_ga;
+    uint64_t m;            // pairs this round
+    int jc;                // columns per thread
+    const Fr* chal;
+    FrTab bI;
+    const Fr* bJ;          // J entries
+    const Fr* rp;          // r'
+    Fr* part;              // partials of this kernel
+};
+
+__device__ __forceinline__ FrTab aux_col(const BinArgs& a, int k, int j) {
+    FrTab t;
+    t.p = a.aux + (uint64_t)(k * a.nbits + j) * 8 * a.ps;
+    t.ps = a.ps;
+    return t;
+}
+
+// sum of beta_J(j) over the set bits of `mask`
+__device__ __forceinline__ Fr masked_sum(const Fr* bJ, uint64_t mask, int nbits) {
+    Fr s = fr_zero();
+    for (int j = 0; j < nbits; ++j)
+        if ((mask >> j) & 1) s = fr_add(s, bJ[j]);
+    return s;
+}
+
+// Round 0: both halves are bits, a(x)^2 - a(x) = (x^2 - x) [lo != hi]; contributes
+// 2 beta_I(2, i') C(i') at x = 2 and 6 beta_I(3, i') C(i') at x = 3,
+// C = sum_j beta_J(j) ([z bits differ] + r' [g bits differ]).
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin0(BinArgs a) {
+    __shared__ uint32_t red[64];
+    __shared__ Fr sbj[64];
+    if (threadIdx.x < 64) sbj[threadIdx.x] = threadIdx.x < (unsigned)a.nbits ? a.bJ[threadIdx.x] : fr_zero();
+    __syncthreads();
+    Fr acc2 = fr_zero(), acc3 = fr_zero();
+    const uint64_t m = a.m;
+    const uint64_t keep = a.nbits >= 64 ? ~(uint64_t)0 : (((uint64_t)1 << a.nbits) - 1);
+    Fr rp = *a.rp;
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
+         b += (uint64_t)gridDim.x * blockDim.x) {
+        uint64_t dz = ((uint64_t)a.z[b] ^ (uint64_t)a.z[b + m]) & keep;
+        Fr c = masked_sum(sbj, dz, a.nbits);
+        if (a.has_ga) {
+            uint64_t dg = ((uint64_t)a.ga[b] ^ (uint64_t)a.ga[b + m]) & keep;
+            c = fr_add(c, fr_mul(rp, masked_sum(sbj, dg, a.nbits)));
+        }
+        Fr lo = tab_ld(a.bI, b), hi = tab_ld(a.bI, b + m);
+        Fr d = fr_sub(hi, lo);
+        Fr b2 = fr_add(hi, d), b3 = fr_add(b2, d);
+        Fr c2 = fr_dbl(c);                       // (x^2 - x) = 2 at x = 2
+        Fr c6 = fr_add(fr_dbl(c2), c2);          // 6 at x = 3
+        acc2 = fr_add(acc2, fr_mul(b2, c2));
+        acc3 = fr_add(acc3, fr_mul(b3, c6));
+    }
+    Fr s2 = block_sum(acc2, red);
+    Fr s3 = block_sum(acc3, red);
+    if (threadIdx.x == 0) {
+        Fr* p = a.part + (uint64_t)blockIdx.x * 4;
+        p[0] = fr_zero();
+        p[1] = fr_zero();
+        p[2] = s2;
+        p[3] = s3;
+    }
+}
+
+// After the first challenge v: aux(k, v, i', j) in {0, 1, v, 1 - v} by (bit_lo, bit_hi)
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat(BinArgs a) {
+    const uint64_t m = a.m;   // rows written = D / 2
+    Fr v = *a.chal;
+    Fr one = fr_one();
+    Fr omv = fr_sub(one, v);
+    int j0 = blockIdx.y * a.jc, j1 = j0 + a.jc;
+    if (j1 > a.nbits) j1 = a.nbits;
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
+         b += (uint64_t)gridDim.x * blockDim.x) {
+        for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+            const int64_t* src = k == 0 ? a.z : a.ga;
+            uint64_t lo = (uint64_t)src[b], hi = (uint64_t)src[b + m];
+            for (int j = j0; j < j1; ++j) {
+                int bl = (lo >> j) & 1, bh = (hi >> j) & 1;
+                Fr val = bl == bh ? (bl ? one : fr_zero()) : (bh ? v : omv);
+                tab_st(aux_col(a, k, j), b, val);
+            }
+        }
+    }
+}
+
+// Rounds t >= 1: per (i', j) the pair (lo, hi) of aux~(k, v.., x, i', j); the folded
+// tables are written back when FOLD.  Per thread: sum over its columns of
+// beta_J(j) (a^2 - a) at x = 0..3 for both slices, then times beta_I(x, i').
+template <bool FOLD>
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin(BinArgs a) {
+    __shared__ uint32_t red[64];
+    const uint64_t m = a.m;
+    Fr v = fr_zero();
+    if (FOLD) v = *a.chal;
+    Fr rp = *a.rp;
+    int j0 = blockIdx.y * a.jc, j1 = j0 + a.jc;
+    if (j1 > a.nbits) j1 = a.nbits;
+    Fr tot[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) tot[x] = fr_zero();
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
+         b += (uint64_t)gridDim.x * blockDim.x) {
+        Fr acc[2][4];
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) acc[k][x] = fr_zero();
+        for (int j = j0; j < j1; ++j) {
+            Fr bj = a.bJ[j];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                if (k == 1 && !a.has_ga) break;
+                Fr lo, hi, e[4];
+                lin_pair<FOLD>(aux_col(a, k, j), b, m, v, lo, hi);
+                line4(lo, hi, e);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    Fr q = fr_sub(fr_sqr(e[x]), e[x]);
+                    acc[k][x] = fr_add(acc[k][x], fr_mul(bj, q));
+                }
+            }
+        }
+        Fr lo = tab_ld(a.bI, b), hi = tab_ld(a.bI, b + m), bi[4];
+        line4(lo, hi, bi);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            Fr s = acc[0][x];
+            if (a.has_ga) s = fr_add(s, fr_mul(rp, acc[1][x]));
+            tot[x] = fr_add(tot[x], fr_mul(bi[x], s));
+        }
+    }
+    const uint64_t blk = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        Fr s = block_sum(tot[x], red);
+        if (threadIdx.x == 0) a.part[blk * 4 + x] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// tail: last fold of the i-tables, the j-rounds, finals, merge
+// ---------------------------------------------------------------------------
+struct TailArgs {
+    ZkTabs tabs;
+    BinArgs bin;          // aux planes, z/ga, bJ
+    int li, lj, q_bits, r_bits;
+    DevState* st;
+    int chal_v;           // index of the first round challenge (i-rounds, then j-rounds)
+    int chal_rho;         // rho0..2, then the merge challenges
+    uint32_t rounds_off;  // g's of the combined sumcheck (all rounds)
+    uint32_t finals_off;
+    uint32_t merge_claim_off, merge_rounds_off, merge_finals_off;
+};
+
+constexpr int TAIL_THREADS = 128;
+
+__device__ __forceinline__ Fr tail_block_sum(Fr x, uint32_t* red) { return block_sum(x, red); }
+
+__global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
+    __shared__ uint32_t red[64];
+    __shared__ uint8_t lds[TS_LDS_BYTES];
+    __shared__ Fr A0[64], A1[64], S[64], SP[64], BJ[64];   // tables over j
+    __shared__ Fr M[128], E[128];                           // merge tables over (k, j)
+    __shared__ Fr sc[LIN_TABLES];
+    __shared__ Fr g[4];
+    __shared__ Fr vsh;
+    __shared__ Fr rho[3];
+    const int tid = threadIdx.x;
+    DevState* st = a.st;
+    const int J = 1 << a.lj, nbits = a.q_bits + a.r_bits;
+    const Fr one = fr_one();
+    Fr vlast = fr_zero();
+    if (a.li >= 1) vlast = st->chal[a.chal_v + a.li - 1];
+
+    // scalars: the D-sized tables at the full i-point
+    if (tid < LIN_TABLES) {
+        Fr lo = tab_ld(a.tabs.t[tid], 0);
+        bool present = a.bin.has_ga || !(tid == T_BGA || tid == T_GA || tid == T_BGZ || tid == T_GAP);
+        if (!present) lo = fr_zero();
+        else if (a.li >= 1) {
+            Fr hi = tab_ld(a.tabs.t[tid], 1);
+            lo = fr_add(lo, fr_mul(vlast, fr_sub(hi, lo)));
+        }
+        sc[tid] = lo;
+    }
+    // tables over j
+    if (tid < 64) {
+        const int j = tid;
+        Fr a0 = fr_zero(), a1 = fr_zero(), s = fr_zero(), sp = fr_zero(), bj = fr_zero();
+        if (j < J) bj = a.bin.bJ[j];
+        if (j < nbits) {
+            for (int k = 0; k < (a.bin.has_ga ? 2 : 1); ++k) {
+                Fr val;
+                if (a.li == 0) {
+                    const int64_t* src = k == 0 ? a.bin.z : a.bin.ga;
+                    val = (((uint64_t)src[0] >> j) & 1) ? one : fr_zero();
+                } else {
+                    FrTab col = aux_col(a.bin, k, j);
+                    val = tab_ld(col, 0);
+                    if (a.li >= 2) {
+                        Fr hi = tab_ld(col, 1);
+                        val = fr_add(val, fr_mul(vlast, fr_sub(hi, val)));
+                    }
+                }
+                if (k == 0) a0 = val;
+                else a1 = val;
+            }
+            // s_{Q+R}(j) and s'(j) (Sec. 3.1, App. A)
+            if (j < nbits - 1) s = fr_from_i64((int64_t)1 << j);
+            else s = fr_from_i64(j == 63 ? INT64_MIN : -((int64_t)1 << j));
+            if (j == a.r_bits - 1) sp = one;
+            else if (j >= a.r_bits && j < nbits - 1) sp = fr_from_i64((int64_t)1 << (j - a.r_bits));
+            else if (j == nbits - 1) sp = fr_from_i64(-((int64_t)1 << (a.q_bits - 1)));
+        }
+        A0[j] = a0;
+        A1[j] = a1;
+        S[j] = s;
+        SP[j] = sp;
+        BJ[j] = bj;
+        M[j] = a0;
+        M[64 + j] = a1;
+    }
+    __syncthreads();
+    // coefficients that stay fixed during the j-rounds
+    const Fr cZ = sc[T_BZ];                          // r^2 beta_Z(v)
+    const Fr cA = fr_mul(sc[T_BA], sc[T_NS]);        // r beta_A(v) (1 - sign(v))
+    const Fr cGA = sc[T_BGA];
+    const Fr cGZ = fr_mul(sc[T_BGZ], sc[T_NS]);
+    const Fr cB0 = sc[T_BI];                         // beta_I(v)
+    const Fr cB1 = fr_mul(st->weights[4], sc[T_BI]); // r' beta_I(v)
+
+    int cur = J;
+    for (int t = 0; t < a.lj; ++t) {
+        const int half = cur >> 1;
+        Fr f[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) f[x] = fr_zero();
+        if (tid < half) {
+            Fr a0[4], a1[4], s[4], sp[4], bj[4];
+            line4(A0[tid], A0[tid + half], a0);
+            line4(A1[tid], A1[tid + half], a1);
+            line4(S[tid], S[tid + half], s);
+            line4(SP[tid], SP[tid + half], sp);
+            line4(BJ[tid], BJ[tid + half], bj);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                Fr lin0 = fr_add(fr_mul(cZ, s[x]), fr_mul(cA, sp[x]));
+                Fr lin1 = fr_add(fr_mul(cGA, s[x]), fr_mul(cGZ, sp[x]));
+                Fr q0 = fr_sub(fr_sqr(a0[x]), a0[x]);
+                Fr q1 = fr_sub(fr_sqr(a1[x]), a1[x]);
+                Fr binp = fr_mul(bj[x], fr_add(fr_mul(cB0, q0), fr_mul(cB1, q1)));
+                f[x] = fr_add(fr_add(fr_mul(lin0, a0[x]), fr_mul(lin1, a1[x])), binp);
+            }
+        }
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            Fr s = block_sum(f[x], red);
+            if (tid == 0) g[x] = s;
+        }
+        if (tid == 0)
+            vsh = dev_finalise_round(st, g, 4, a.rounds_off + (uint32_t)(a.li + t) * 128,
+                                     a.chal_v + a.li + t, lds);
+        __syncthreads();
+        Fr v = vsh;
+        if (tid < half) {
+            A0[tid] = fr_add(A0[tid], fr_mul(v, fr_sub(A0[tid + half], A0[tid])));
+            A1[tid] = fr_add(A1[tid], fr_mul(v, fr_sub(A1[tid + half], A1[tid])));
+            S[tid] = fr_add(S[tid], fr_mul(v, fr_sub(S[tid + half], S[tid])));
+            SP[tid] = fr_add(SP[tid], fr_mul(v, fr_sub(SP[tid + half], SP[tid])));
+            BJ[tid] = fr_add(BJ[tid], fr_mul(v, fr_sub(BJ[tid + half], BJ[tid])));
+        }
+        __syncthreads();
+        cur = half;
+    }
+    // finals: aux~(0, v, wbar), aux~(1, v, wbar), aux~(0, v, Q+R-1) = 1 - (1 - sign)(v)
+    if (tid == 0) {
+        Fr fin[3] = {A0[0], A1[0], fr_sub(one, sc[T_NS])};
+        for (int k = 0; k < 3; ++k) st->scal[4 + k] = fin[k];
+        dev_absorb_frs(st, "f", 1, fin, 3, st->proof + a.finals_off, lds);
+        for (int k = 0; k < 3; ++k) rho[k] = dev_challenge(st, a.chal_rho + k);
+        Fr mc = fr_add(fr_add(fr_mul(rho[0], fin[0]), fr_mul(rho[1], fin[1])), fr_mul(rho[2], fin[2]));
+        st->claim = mc;
+        ts::fr_to_le(mc, st->proof + a.merge_claim_off);
+    }
+    // beta~(wbar, .) over j, built in place from the last coordinate upwards (into E[0..J))
+    if (tid == 0) E[0] = one;
+    __syncthreads();
+    {
+        int size = 1;
+        for (int k = a.lj - 1; k >= 0; --k) {
+            Fr u = st->chal[a.chal_v + a.li + k];
+            Fr e, hi;
+            if (tid < size) {
+                e = E[tid];
+                hi = fr_mul(e, u);
+            }
+            __syncthreads();
+            if (tid < size) {
+                E[tid + size] = hi;
+                E[tid] = fr_sub(e, hi);
+            }
+            size <<= 1;
+            __syncthreads();
+        }
+    }
+    // E(0, j) = rho0 beta(wbar, j) + rho2 [j == Q+R-1],  E(1, j) = rho1 beta(wbar, j)
+    Fr bw = fr_zero();
+    if (tid < 64 && tid < J) bw = E[tid];
+    __syncthreads();
+    if (tid < 64) {
+        Fr e0 = fr_mul(rho[0], bw);
+        if (tid == nbits - 1) e0 = fr_add(e0, rho[2]);
+        E[tid] = tid < J ? e0 : fr_zero();
+        E[64 + tid] = tid < J ? fr_mul(rho[1], bw) : fr_zero();
+    }
+    __syncthreads();
+    // merge sumcheck over (k, j): k first (pairs index c with 64 + c), then the lj
+    // variables of j inside the first J entries of each half
+    // Compact the tables to 2J entries when J < 64 so that halves are contiguous.
+    if (J < 64) {
+        Fr m1 = fr_zero(), e1 = fr_zero();
+        if (tid < J) {
+            m1 = M[64 + tid];
+            e1 = E[64 + tid];
+        }
+        __syncthreads();
+        if (tid < J) {
+            M[J + tid] = m1;
+            E[J + tid] = e1;
+        }
+        __syncthreads();
+    }
+    cur = 2 * J;
+    for (int t = 0; t < 1 + a.lj; ++t) {
+        const int half = cur >> 1;
+        Fr f[3];
+#pragma unroll
+        for (int x = 0; x < 3; ++x) f[x] = fr_zero();
+        if (tid < half) {
+            Fr mlo = M[tid], mhi = M[tid + half], elo = E[tid], ehi = E[tid + half];
+            Fr md = fr_sub(mhi, mlo), ed = fr_sub(ehi, elo);
+            f[0] = fr_mul(mlo, elo);
+            f[1] = fr_mul(mhi, ehi);
+            f[2] = fr_mul(fr_add(mhi, md), fr_add(ehi, ed));
+        }
+#pragma unroll
+        for (int x = 0; x < 3; ++x) {
+            Fr s = block_sum(f[x], red);
+            if (tid == 0) g[x] = s;
+        }
+        if (tid == 0)
+            vsh = dev_finalise_round(st, g, 3, a.merge_rounds_off + (uint32_t)t * 96, a.chal_rho + 3 + t, lds);
+        __syncthreads();
+        Fr v = vsh;
+        if (tid < half) {
+            M[tid] = fr_add(M[tid], fr_mul(v, fr_sub(M[tid + half], M[tid])));
+            E[tid] = fr_add(E[tid], fr_mul(v, fr_sub(E[tid + half], E[tid])));
+        }
+        __syncthreads();
+        cur = half;
+    }
+    if (tid == 0) {
+        Fr fin[2] = {M[0], E[0]};
+        st->scal[7] = fin[0];
+        st->scal[8] = fin[1];
+        dev_absorb_frs(st, "f", 1, fin, 2, st->proof + a.merge_finals_off, lds);
+    }
+}
+
+unsigned blocks_for(uint64_t n, unsigned cap) {
+    uint64_t b = (n + ZK_BLOCK - 1) / ZK_BLOCK;
+    if (b < 1) b = 1;
+    if (b > cap) b = cap;
+    return (unsigned)b;
+}
+
+int log2u(uint64_t x) {
+    int l = 0;
+    while (((uint64_t)1 << l) < x) ++l;
+    return l;
+}
+
+const uint32_t SC_MAGIC = 0x43534B5Au;
+
+}  // namespace
+
 int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q, int R) {
-    return ZKDL_EINVAL;
+    const int nbits = Q + R;
+    const int li = log2u(D);
+    int lj = 0;
+    while ((1 << lj) < nbits) ++lj;
+    const int J = 1 << lj;
+    const int has_ga = ga_dev != nullptr;
+    const int need = 6 * li + 3 * lj + 6;
+    if (ctx->n_chal + need > ZK_MAX_CHAL) return ZKDL_EINVAL;
+    const int c0 = ctx->n_chal;
+    const int c_uz = c0, c_ua = c0 + li, c_uga = c0 + 2 * li, c_ugz = c0 + 3 * li, c_ubin = c0 + 4 * li;
+    const int c_r = c0 + 5 * li + lj, c_v = c_r + 2, c_rho = c_v + li + lj;
+    ctx->n_chal += need;
+
+    // proof layout
+    const uint32_t claims_off = (uint32_t)ctx->proof_len;
+    ctx->proof_len += 4 * 32;
+    uint32_t hdr[4] = {SC_MAGIC, 3, 3, (uint32_t)(li + lj)};
+    zk_write_proof_words(ctx, hdr, 4);
+    const uint32_t claim0_off = (uint32_t)ctx->proof_len;
+    const uint32_t rounds_off = claim0_off + 32;
+    const uint32_t finals_off = rounds_off + (uint32_t)(li + lj) * 128;
+    ctx->proof_len = finals_off + 3 * 32;
+    uint32_t mhdr[4] = {SC_MAGIC, 2, 2, (uint32_t)(1 + lj)};
+    zk_write_proof_words(ctx, mhdr, 4);
+    const uint32_t mclaim_off = (uint32_t)ctx->proof_len;
+    const uint32_t mrounds_off = mclaim_off + 32;
+    const uint32_t mfinals_off = mrounds_off + (uint32_t)(1 + lj) * 96;
+    ctx->proof_len = mfinals_off + 2 * 32;
+    if (ctx->proof_len > (size_t)ZK_PROOF_CAP) return ZKDL_ESMALL;
+
+    DevState* st = ctx->dev;
+    zk_launch_draw(ctx, c0, 5 * li + lj);
+
+    // memory: 10 D-sized tables, beta_J, aux planes (2 * nbits columns of D/2 rows)
+    const uint64_t rows = D >= 2 ? D / 2 : 1;
+    const uint64_t aux_elems = (uint64_t)(has_ga ? 2 : 1) * nbits * rows;
+    void* mem = zk_alloc(ctx, ((uint64_t)LIN_TABLES * D + 64 + (li >= 1 ? aux_elems : 0)) * 32);
+    if (!mem) return ZKDL_ENOMEM;
+    uint32_t* base = (uint32_t*)mem;
+    ZkTabs tabs;
+    for (int k = 0; k < LIN_TABLES; ++k) {
+        tabs.t[k] = make_tab(base, D);
+        base += 8 * D;
+    }
+    Fr* bJ = (Fr*)base;
+    base += 8 * 64;
+    uint32_t* aux = base;
+
+    int rc = zk_build_beta(ctx, st->chal + c_uz, li, tabs.t[T_BZ]);
+    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ua, li, tabs.t[T_BA]);
+    if (rc == ZKDL_OK && has_ga) rc = zk_build_beta(ctx, st->chal + c_uga, li, tabs.t[T_BGA]);
+    if (rc == ZKDL_OK && has_ga) rc = zk_build_beta(ctx, st->chal + c_ugz, li, tabs.t[T_BGZ]);
+    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ubin, li, tabs.t[T_BI]);
+    // beta_J as an array of structures: one plane of J elements read through FrTab, then copied
+    FrTab bj_soa = make_tab(aux, J);   // aux is not in use yet (or absent: then scratch below)
+    void* bj_tmp = nullptr;
+    if (li < 1) {
+        bj_tmp = zk_alloc(ctx, 64 * 32);
+        if (!bj_tmp) rc = ZKDL_ENOMEM;
+        bj_soa = make_tab(bj_tmp, J);
+    }
+    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ubin + li, lj, bj_soa);
+    if (rc != ZKDL_OK) {
+        zk_free(ctx, bj_tmp);
+        zk_free(ctx, mem);
+        return rc;
+    }
+    zk_launch_soa_to_aos(ctx, bj_soa, J, bJ);
+
+    PrepArgs pa;
+    pa.z = z_dev;
+    pa.ga = ga_dev;
+    pa.D = D;
+    pa.nbits = nbits;
+    pa.r_bits = R;
+    pa.tabs = tabs;
+    pa.part = ctx->partials;
+    pa.st = st;
+    unsigned nb = blocks_for(D, ZK_MAX_PART_BLOCKS);
+    hipLaunchKernelGGL(k_zk_prepare, dim3(nb), dim3(ZK_BLOCK), 0, ctx->stream, pa);
+    ClaimsArgs ca;
+    ca.part = ctx->partials;
+    ca.nblk = (int)nb;
+    ca.st = st;
+    ca.claims_off = claims_off;
+    ca.claim0_off = claim0_off;
+    ca.chal_r = c_r;
+    hipLaunchKernelGGL(k_zk_claims, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ca);
+    hipLaunchKernelGGL(k_zk_scale, dim3(blocks_for(D, 65536)), dim3(ZK_BLOCK), 0, ctx->stream, tabs, D,
+                       (const Fr*)st->weights, has_ga);
+
+    BinArgs ba;
+    ba.z = z_dev;
+    ba.ga = ga_dev;
+    ba.aux = aux;
+    ba.ps = rows;
+    ba.nbits = nbits;
+    ba.has_ga = has_ga;
+    ba.bI = tabs.t[T_BI];
+    ba.bJ = bJ;
+    ba.rp = &st->weights[4];
+    ba.jc = nbits;
+    ba.chal = nullptr;
+    ba.m = 0;
+    ba.part = nullptr;
+
+    for (int t = 0; t < li; ++t) {
+        const uint64_t m = D >> (t + 1);
+        LinArgs la;
+        la.tabs = tabs;
+        la.m = m;
+        la.chal = t > 0 ? &st->chal[c_v + t - 1] : nullptr;
+        la.part = ctx->partials;
+        la.has_ga = has_ga;
+        unsigned nb_lin = blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
+        if (t == 0) hipLaunchKernelGGL(k_zk_lin<false>, dim3(nb_lin), dim3(ZK_BLOCK), 0, ctx->stream, la);
+        else hipLaunchKernelGGL(k_zk_lin<true>, dim3(nb_lin), dim3(ZK_BLOCK), 0, ctx->stream, la);
+        ba.m = m;
+        ba.part = ctx->partials + (uint64_t)nb_lin * 4;
+        unsigned nb_bin;
+        if (t == 0) {
+            nb_bin = blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
+            hipLaunchKernelGGL(k_zk_bin0, dim3(nb_bin), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+        } else {
+            // few rows: split the columns over more threads
+            int jc = nbits;
+            while ((uint64_t)((nbits + jc - 1) / jc) * m < 32768 && jc > 1) jc = (jc + 1) / 2;
+            unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
+            unsigned bx = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / chunks);
+            ba.jc = jc;
+            ba.chal = t >= 2 ? &st->chal[c_v + t - 1] : nullptr;
+            if (t >= 2) hipLaunchKernelGGL(k_zk_bin<true>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            else hipLaunchKernelGGL(k_zk_bin<false>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            nb_bin = bx * chunks;
+        }
+        zk_launch_finalise(ctx, (int)(nb_lin + nb_bin), 4, c_v + t, rounds_off + (uint32_t)t * 128, 0, 0);
+        if (t == 0) {
+            // bind the first challenge: bits -> field elements
+            int jc = nbits;
+            while ((uint64_t)((nbits + jc - 1) / jc) * m < 32768 && jc > 1) jc = (jc + 1) / 2;
+            unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
+            ba.jc = jc;
+            ba.chal = &st->chal[c_v];
+            hipLaunchKernelGGL(k_zk_mat, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+        }
+    }
+    TailArgs ta;
+    ta.tabs = tabs;
+    ta.bin = ba;
+    ta.li = li;
+    ta.lj = lj;
+    ta.q_bits = Q;
+    ta.r_bits = R;
+    ta.st = st;
+    ta.chal_v = c_v;
+    ta.chal_rho = c_rho;
+    ta.rounds_off = rounds_off;
+    ta.finals_off = finals_off;
+    ta.merge_claim_off = mclaim_off;
+    ta.merge_rounds_off = mrounds_off;
+    ta.merge_finals_off = mfinals_off;
+    hipLaunchKernelGGL(k_zk_tail, dim3(1), dim3(TAIL_THREADS), 0, ctx->stream, ta);
+    zk_free(ctx, bj_tmp);
+    zk_free(ctx, mem);
+    return ZKDL_OK;
 }

@@ -94,6 +94,7 @@ int zk_build_beta(zkdl_ctx* ctx, const Fr* point, int m, FrTab out);
 int zk_partial_eval(zkdl_ctx* ctx, int kind, const void* src, uint64_t O, uint64_t A, uint64_t I,
                     FrTab beta, FrTab out);
 void zk_launch_broadcast_rows(zkdl_ctx* ctx, FrTab src, uint64_t rows, uint64_t inner, FrTab out);
+void zk_launch_soa_to_aos(zkdl_ctx* ctx, FrTab in, int n, Fr* out);
 void zk_launch_shift_rows(zkdl_ctx* ctx, FrTab src, uint64_t rows, uint64_t inner, uint32_t period,
                           FrTab out);
 

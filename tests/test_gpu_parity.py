@@ -182,3 +182,97 @@ def test_chained_calls_share_one_transcript(lib, ctx):
     b1, _, _ = P.product_prove([fr_array_from_le(r, n) for r in raws], ots)
     b2, _, _ = P.product_prove([fr_array_from_le(raws[0], n)], ots)
     assert g1["proof"] == b1 and g2["proof"] == b2 and tr.digest() == ots.digest()
+
+
+ZKRELU_CASES = [
+    (1, True, 32, 16), (2, True, 32, 16), (4, False, 32, 16), (64, True, 32, 16),
+    (16, True, 5, 3), (8, True, 4, 4), (4, True, 48, 16), (512, False, 32, 16), (1024, True, 32, 16),
+]
+
+
+@pytest.mark.parametrize("d_len,with_ga,q,r", ZKRELU_CASES)
+def test_zkrelu(lib, ctx, d_len, with_ga, q, r):
+    say(f"zkrelu D={d_len} ga={with_ga} Q={q} R={r}")
+    rng = np.random.default_rng(d_len * 7 + q)
+    lim = 1 << (q + r - 1)
+    z = rng.integers(-lim, lim, d_len, dtype=np.int64)
+    ga = rng.integers(-lim, lim, d_len, dtype=np.int64) if with_ga else None
+    edge = [0, -1, lim - 1, -lim, 1 << (r - 1), (1 << (r - 1)) - 1, -(1 << (r - 1)), -(1 << (r - 1)) - 1]
+    z[:min(d_len, len(edge))] = edge[:min(d_len, len(edge))]
+    tr = lib.Transcript(21)
+    got = lib.zkrelu_prove(ctx, z, ga, tr, q, r)
+    ots = OracleTranscript(21)
+    buf, info = P.zkrelu_prove(z.tolist(), ga.tolist() if with_ga else None, q, r, ots)
+    assert got["points"] == ots.challenges
+    assert got["proof"] == buf
+    assert got["claims"] == info["c_in"]
+    assert tr.digest() == ots.digest()
+
+
+def test_zkrelu_device_inputs_and_range_error(lib, ctx):
+    import torch
+    say("zkrelu device inputs / range error")
+    rng = np.random.default_rng(8)
+    z = rng.integers(-2 ** 47, 2 ** 47, 256, dtype=np.int64)
+    ga = rng.integers(-2 ** 47, 2 ** 47, 256, dtype=np.int64)
+    tr = lib.Transcript(2)
+    got = lib.zkrelu_prove(ctx, torch.from_numpy(z).cuda(), torch.from_numpy(ga).cuda(), tr)
+    ots = OracleTranscript(2)
+    buf, _ = P.zkrelu_prove(z.tolist(), ga.tolist(), 32, 16, ots)
+    assert got["proof"] == buf and tr.digest() == ots.digest()
+    for bad_z, bad_g in ((1 << 47, 0), (0, -(1 << 47) - 1)):
+        z2, g2 = z.copy(), ga.copy()
+        z2[100] += 0
+        z2[17] = bad_z if bad_z else z2[17]
+        g2[200] = bad_g if bad_g else g2[200]
+        tr = lib.Transcript(2)
+        before = tr.digest()
+        with pytest.raises(lib.ZkdlError) as ei:
+            lib.zkrelu_prove(ctx, z2, g2, tr)
+        assert ei.value.code == -2          # ZKDL_ERANGE, as the oracle's ValueError
+        assert tr.digest() == before        # a failed call leaves the transcript untouched
+        with pytest.raises(ValueError):
+            P.zkrelu_prove(z2.tolist(), g2.tolist(), 32, 16, OracleTranscript(2))
+
+
+def to_cuda_witness(wit):
+    import torch
+    out = {k: wit[k] for k in ("L", "B", "width", "T", "Q", "R")}
+    for k in ("A", "W", "GZ", "Zr", "GA"):
+        out[k] = torch.from_numpy(np.ascontiguousarray(wit[k])).cuda()
+    return out
+
+
+@pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 32, 8, 1), (1, 16, 2, 1)])
+def test_aggregate(lib, ctx, layers, width, batch, steps):
+    say(f"aggregate L={layers} w={width} B={batch} T={steps}")
+    wit = fcnn_window(CONFIG_SEED + 50 + layers, layers, width, batch, steps)
+    tr = lib.Transcript(33)
+    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr)
+    ots = OracleTranscript(33)
+    buf, _ = P.aggregate_prove(wit, ots)
+    assert got["points"] == ots.challenges
+    assert got["proof"] == buf
+    assert tr.digest() == ots.digest()
+    P.aggregate_verify(got["proof"], OracleTranscript(33))
+
+
+def test_config1_fc_layer_plus_relu(lib, ctx):
+    """One FC layer + ReLU: X 16x256, W 256x256, zkReLU over Z with Q=32 (forward only)."""
+    import torch
+    say("config 1")
+    lay = fc_relu_layer(CONFIG_SEED + 1)
+    tr = lib.Transcript(CONFIG_SEED + 1)
+    x = lib.tensor_wrap_int(ctx, torch.from_numpy(lay["X"]).cuda(), (1, 16, 256))
+    w = lib.tensor_wrap_int(ctx, torch.from_numpy(lay["W"]).cuda(), (1, 256, 256))
+    g1 = lib.sumcheck_matmul(ctx, x, w, tr)
+    g2 = lib.zkrelu_prove(ctx, torch.from_numpy(lay["Z"]).cuda().reshape(-1), None, tr)
+    ots = OracleTranscript(CONFIG_SEED + 1)
+    b1, p1, _ = P.matmul_prove(fr_array(lay["X"]), [1, 16, 256], fr_array(lay["W"]), [1, 256, 256], ots)
+    b2, info = P.zkrelu_prove(lay["Z"].reshape(-1).tolist(), None, 32, 16, ots)
+    assert g1["proof"] == b1 and g2["proof"] == b2
+    assert tr.digest() == ots.digest()
+    # the matmul's claim on Y is the MLE of the very Z that zkReLU decomposes
+    from oracle.mle import mle_eval
+    pts = g1["points"]
+    assert g1["claims"][0] == mle_eval(fr_array(lay["Z"]), pts[:4 + 8])
