@@ -67,9 +67,9 @@ def matmul_prove(x0, shape0, x1, shape1, ts):
     n_, d2_, d3 = shape1
     assert n == n_ and d2 == d2_
     ts.absorb_u32(b"sumcheck_matmul", [n, d1, d2, d3])
-    w = ts.challenges_vec(ilog2(n))
-    u0 = ts.challenges_vec(ilog2(d1))
-    u1 = ts.challenges_vec(ilog2(d3))
+    ln, l1, l3 = ilog2(n), ilog2(d1), ilog2(d3)
+    pt = ts.challenges_vec(ln + l1 + l3)          # the point (w, u0, u1): one draw
+    w, u0, u1 = pt[:ln], pt[ln:ln + l1], pt[ln + l1:]
     t0, _ = partial_eval(x0, [n, d1, d2], 1, 2, u0)          # [N, D2]
     t1, _ = partial_eval(x1, [n, d2, d3], 2, 3, u1)          # [N, D2]
     tb = np.repeat(beta_table(w), d2)                         # beta~(w,n), every i
@@ -82,9 +82,9 @@ def matmul_verify(buf, n, d1, d2, d3, ts):
     assert proof.n_finals == 3 and proof.degree == 3
     assert len(proof.rounds) == ilog2(n) + ilog2(d2)
     ts.absorb_u32(b"sumcheck_matmul", [n, d1, d2, d3])
-    w = ts.challenges_vec(ilog2(n))
-    u0 = ts.challenges_vec(ilog2(d1))
-    u1 = ts.challenges_vec(ilog2(d3))
+    ln, l1, l3 = ilog2(n), ilog2(d1), ilog2(d3)
+    pt = ts.challenges_vec(ln + l1 + l3)          # the point (w, u0, u1): one draw
+    w, u0, u1 = pt[:ln], pt[ln:ln + l1], pt[ln + l1:]
     claim, vs = verify_rounds(proof, ts)
     fb, f0, f1 = proof.finals
     assert fb == beta_point(w, vs[:len(w)]), "beta final is not beta~(w, v_n)"
@@ -205,16 +205,13 @@ def zkrelu_prove(z, ga, q, r_bits, ts):
     li, lj = ilog2(d_len), ilog2(j_pad)
     b = q + r_bits
     ts.absorb_u32(b"zkrelu", [li, q, r_bits, 1 if has_ga else 0])
-    u_z = ts.challenges_vec(li)
-    u_a = ts.challenges_vec(li)
-    u_ga = ts.challenges_vec(li)
-    u_gz = ts.challenges_vec(li)
-    u_bin = ts.challenges_vec(li + lj)
+    pt = ts.challenges_vec(5 * li + lj)           # all five points: one draw
+    u_z, u_a, u_ga, u_gz, u_bin = (pt[:li], pt[li:2 * li], pt[2 * li:3 * li], pt[3 * li:4 * li],
+                                   pt[4 * li:])
     c_in = [mle_eval(fr_array(wit["Z"]), u_z), mle_eval(fr_array(wit["A"]), u_a),
             mle_eval(fr_array(wit["GA"]), u_ga), mle_eval(fr_array(wit["GZ"]), u_gz)]
     ts.absorb_fr(b"c", c_in)
-    r = ts.challenge()
-    rp = ts.challenge()
+    r, rp = ts.challenges_vec(2)
 
     def over_i(col):      # a table of D values, constant in j
         return np.repeat(np.asarray(col, dtype=object), j_pad)
@@ -284,14 +281,11 @@ def zkrelu_verify(buf, ts, off=0):
     assert proof.degree == 3 and len(proof.rounds) == li + lj and proof.n_finals == 3
     assert merge.degree == 2 and len(merge.rounds) == 1 + lj and merge.n_finals == 2
     ts.absorb_u32(b"zkrelu", [li, q, r_bits, has_ga])
-    u_z = ts.challenges_vec(li)
-    u_a = ts.challenges_vec(li)
-    u_ga = ts.challenges_vec(li)
-    u_gz = ts.challenges_vec(li)
-    u_bin = ts.challenges_vec(li + lj)
+    pt = ts.challenges_vec(5 * li + lj)           # all five points: one draw
+    u_z, u_a, u_ga, u_gz, u_bin = (pt[:li], pt[li:2 * li], pt[2 * li:3 * li], pt[3 * li:4 * li],
+                                   pt[4 * li:])
     ts.absorb_fr(b"c", c_in)
-    r = ts.challenge()
-    rp = ts.challenge()
+    r, rp = ts.challenges_vec(2)
     r2 = r * r % R_MOD
     expect0 = (r2 * c_in[0] + r * c_in[1] + rp * r2 * c_in[2] + rp * r * c_in[3]) % R_MOD
     claim, vs = verify_rounds(proof, ts, absorb_claim=False, expected_claim0=expect0)

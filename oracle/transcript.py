@@ -7,9 +7,14 @@ this build's own; the HIP library implements the same format independently.
 
   state_0           = SHA256("zkdl-mi355x/v1" || u64le(seed))
   absorb(label, m)  : state <- SHA256(state || u8(len label) || label || u64le(len m) || m)
-  challenge()       : d0 = SHA256(state || 0x00); d1 = SHA256(state || 0x01)
-                      c  = int_le(d0 || d1) mod r
-                      state <- SHA256(state || 0x02)
+  challenges(n)     : for i < n: d0 = SHA256(state || 0x00 || u32le(i)),
+                                 d1 = SHA256(state || 0x01 || u32le(i)),
+                                 c_i = int_le(d0 || d1) mod r
+                      then state <- SHA256(state || 0x02)   (n = 0: nothing happens)
+  challenge()       = challenges(1)[0]
+
+The n challenges of one draw depend on the state only, so a point u in F^m is
+one hash latency on a parallel machine, not m.
 
 Field elements are absorbed as 32-byte canonical little-endian strings.
 Test infrastructure; not used by the product.
@@ -41,16 +46,20 @@ class Transcript:
     def absorb_u32(self, label, words):
         self.absorb(label, b"".join(struct.pack("<I", w) for w in words))
 
-    def challenge(self):
-        d0 = hashlib.sha256(self.state + b"\x00").digest()
-        d1 = hashlib.sha256(self.state + b"\x01").digest()
-        c = int.from_bytes(d0 + d1, "little") % R_MOD
-        self.state = hashlib.sha256(self.state + b"\x02").digest()
-        self.challenges.append(c)
-        return c
-
     def challenges_vec(self, n):
-        return [self.challenge() for _ in range(n)]
+        out = []
+        for i in range(n):
+            idx = struct.pack("<I", i)
+            d0 = hashlib.sha256(self.state + b"\x00" + idx).digest()
+            d1 = hashlib.sha256(self.state + b"\x01" + idx).digest()
+            out.append(int.from_bytes(d0 + d1, "little") % R_MOD)
+        if n > 0:
+            self.state = hashlib.sha256(self.state + b"\x02").digest()
+        self.challenges.extend(out)
+        return out
+
+    def challenge(self):
+        return self.challenges_vec(1)[0]
 
     def digest(self):
         return self.state

@@ -59,17 +59,21 @@ extern "C" int zkdl_ctx_trim(zkdl_ctx* ctx) {
 static Fr host_double_mod(const Fr& a) { return fr_add(a, a); }
 
 extern "C" int zkdl_selfcheck_constants(void) {
-    // 2^256, 2^512, 2^768 mod r by repeated doubling of 1
+    // 2^261, 2^522, 2^778 mod r by repeated doubling of 1
     Fr x = fr_zero();
     x.v[0] = 1;
-    for (int i = 0; i < 256; ++i) x = host_double_mod(x);
+    for (int i = 0; i < 261; ++i) x = host_double_mod(x);
     if (!fr_eq(x, fr_const(frc::ONE))) return ZKDL_EINVAL;
-    for (int i = 0; i < 256; ++i) x = host_double_mod(x);
+    for (int i = 0; i < 261; ++i) x = host_double_mod(x);
     if (!fr_eq(x, fr_const(frc::R2))) return ZKDL_EINVAL;
     for (int i = 0; i < 256; ++i) x = host_double_mod(x);
-    if (!fr_eq(x, fr_const(frc::R3))) return ZKDL_EINVAL;
-    // the modulus is 1 mod 2^32, which the reduction step of fr_mul relies on
-    if (frc::MOD[0] != 1u) return ZKDL_EINVAL;
+    if (!fr_eq(x, fr_const(frc::W3))) return ZKDL_EINVAL;
+    // the 29-bit limbs of the modulus are its 32-bit limbs repacked
+    F9 m9 = fr_unpack(fr_const(frc::MOD));
+    for (int i = 0; i < 9; ++i)
+        if (m9.v[i] != frc::MOD9[i]) return ZKDL_EINVAL;
+    // the modulus is 1 mod 2^29, which the reduction step of f9_mul relies on
+    if (frc::MOD9[0] != 1u) return ZKDL_EINVAL;
     return ZKDL_OK;
 }
 
@@ -399,9 +403,12 @@ __global__ void k_absorb_words(DevState* st, AbsorbWordsArg a) {
     for (uint32_t i = 0; i < a.n; ++i)
         for (int b = 0; b < 4; ++b) data[4 * i + b] = (uint8_t)(a.words[i] >> (8 * b));
     uint8_t state[32];
-    for (int i = 0; i < 32; ++i) state[i] = st->ts_state[i];
+    uint32_t w[8];
+    for (int i = 0; i < 8; ++i) w[i] = st->ts_state[i];
+    sha::words_to_bytes(w, state);
     ts::absorb(state, a.label, a.label_len, data, 4 * a.n, lds);
-    for (int i = 0; i < 32; ++i) st->ts_state[i] = state[i];
+    sha::bytes_to_words(state, w);
+    for (int i = 0; i < 8; ++i) st->ts_state[i] = w[i];
 }
 
 // header of a protocol: a label and up to 8 little-endian u32 words, absorbed in stream order
@@ -424,7 +431,7 @@ static int call_begin(zkdl_ctx* ctx, zkdl_transcript* tr) {
     g_patches.clear();
     // state + cleared error word
     memset(ctx->host_stage, 0, 64);
-    memcpy(ctx->host_stage, tr->state, 32);
+    sha::bytes_to_words(tr->state, (uint32_t*)ctx->host_stage);
     ZK_HIP(ctx, hipMemcpyAsync(ctx->dev, ctx->host_stage, 64, hipMemcpyHostToDevice, ctx->stream));
     return ZKDL_OK;
 }
@@ -445,7 +452,7 @@ static int call_end(zkdl_ctx* ctx, zkdl_transcript* tr, uint8_t* proof, size_t* 
     ZK_HIP(ctx, hipStreamSynchronize(ctx->stream));
     const DevState* h = (const DevState*)hs;
     if (h->err & 1u) return ZKDL_ERANGE;
-    memcpy(tr->state, h->ts_state, 32);
+    sha::words_to_bytes(h->ts_state, tr->state);
     int rc = ZKDL_OK;
     if (proof_len) {
         if (!proof || *proof_len < ctx->proof_len) {

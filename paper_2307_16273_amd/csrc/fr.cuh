@@ -1,10 +1,18 @@
 // Arithmetic in the BLS12-381 scalar field Fr (the field F of Sec. 2.4 / Sec. 6)
-// for gfx950: 8 x 32-bit limbs, little-endian, Montgomery form with R = 2^256.
+// for gfx950.
 //
-// The 32x32+64 -> 64 multiply-adds below compile to v_mad_u64_u32.  Because
-// r = 1 (mod 2^32), the Montgomery factor -r^{-1} mod 2^32 is 0xffffffff: the
-// per-row multiplier is a negation and the product with the lowest limb of r is
-// the multiplier itself.
+// Storage: 8 x 32-bit limbs, little-endian, fully reduced, Montgomery form with
+// R = 2^261.  Multiplication unpacks both operands into 9 limbs of 29 bits: a
+// 29 x 29-bit product is below 2^58, so a whole column of the product (up to 9
+// operand products and 9 reduction products) accumulates in one 64-bit register
+// with plain v_mad_u64_u32 and no carry handling.  On gfx950 every VALU
+// instruction issues at the same rate, v_mad_u64_u32 included, and a carry chain
+// through VCC costs an extra instruction plus wait states per product, so the
+// count of instructions decides: 153 multiply-adds and about 60 shifts/masks
+// per product here against about 470 instructions for 8 x 32-bit limbs with
+// explicit carries.  Because r = 1 (mod 2^32), r = 1 (mod 2^29) too: the
+// Montgomery factor -r^{-1} mod 2^29 is all ones, the per-column multiplier is a
+// negation and its product with the lowest limb of r is the multiplier itself.
 //
 // Every function is __host__ __device__ so that the host side of the library
 // (constants, transcript, self-checks) runs the same arithmetic.
@@ -22,15 +30,24 @@ namespace frc {
 // the modulus r
 constexpr uint32_t MOD[8] = {0x00000001u, 0xffffffffu, 0xfffe5bfeu, 0x53bda402u,
                              0x09a1d805u, 0x3339d808u, 0x299d7d48u, 0x73eda753u};
-// 2^256 mod r (Montgomery form of 1), 2^512 mod r, 2^768 mod r; re-derived by
+// 2^261 mod r (Montgomery form of 1), 2^522 mod r, 2^778 mod r; re-derived by
 // repeated modular doubling when a context is created (zkdl_selfcheck_constants)
-constexpr uint32_t ONE[8] = {0xfffffffeu, 0x00000001u, 0x00034802u, 0x5884b7fau,
-                             0xecbc4ff5u, 0x998c4fefu, 0xacc5056fu, 0x1824b159u};
-constexpr uint32_t R2[8] = {0xf3f29c6du, 0xc999e990u, 0x87925c23u, 0x2b6cedcbu,
-                            0x7254398fu, 0x05d31496u, 0x9f59ff11u, 0x0748d9d9u};
-constexpr uint32_t R3[8] = {0x439b73afu, 0xc62c1807u, 0x8cf06990u, 0x1b3e0d18u,
-                            0xc7b5f418u, 0x73d13c71u, 0xc8db33e9u, 0x6e2a5bb9u};
+constexpr uint32_t ONE[8] = {0xffffffbau, 0x00000045u, 0x0072d846u, 0x1a25272eu,
+                             0x5dbeee8bu, 0xfe2eedcdu, 0x9eefbe41u, 0x4d043f42u};
+constexpr uint32_t R2[8] = {0xca71b3c0u, 0x67a6440fu, 0x49d98f66u, 0xc44e2d5eu,
+                            0xe8703b58u, 0x7ddc57c6u, 0x009cf20au, 0x27fd91b3u};
+constexpr uint32_t W3[8] = {0x6dceb833u, 0xb06020dbu, 0xc7e29ae5u, 0xb06c02ccu,
+                            0x3bae542du, 0x9217b092u, 0x413a7a64u, 0x0b29f00eu};
+// r in 9 limbs of 29 bits
+constexpr uint32_t MOD9[9] = {0x00000001u, 0x1ffffff8u, 0x1f96ffbfu, 0x1b4805ffu, 0x1d80553bu,
+                              0x0c0404d0u, 0x1520cce7u, 0x0a6533afu, 0x0073eda7u};
+constexpr uint32_t M29 = 0x1fffffffu;
 }  // namespace frc
+
+// 9 limbs of 29 bits; "normal" means every limb < 2^29
+struct F9 {
+    uint32_t v[9];
+};
 
 FR_HD Fr fr_zero() {
     Fr z;
@@ -117,43 +134,76 @@ FR_HD Fr fr_neg(const Fr& a) { return fr_sub(fr_zero(), a); }
 
 FR_HD Fr fr_dbl(const Fr& a) { return fr_add(a, a); }
 
-// Montgomery product a * b / 2^256 mod r.
-// Requires a < r; b may be any 256-bit value (the running value stays below
-// a + r < 2r), which is what the wide reduction of hash output relies on.
-FR_HD Fr fr_mul(const Fr& a, const Fr& b) {
-    uint32_t t[8];
+// 8 x 32 -> 9 x 29 (any 256-bit value; the top limb gets bits 232..255)
+FR_HD F9 fr_unpack(const Fr& a) {
+    F9 o;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) t[i] = 0;
-    uint32_t t8 = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        // t += a * b[i]
-        uint64_t c = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            c = (uint64_t)a.v[j] * b.v[i] + t[j] + c;
-            t[j] = (uint32_t)c;
-            c >>= 32;
-        }
-        uint64_t top = (uint64_t)t8 + c;  // < 2^33
-        // t += m * r with m = -t[0] mod 2^32, then drop the (now zero) low limb
-        uint32_t m = 0u - t[0];
-        c = (t[0] != 0) ? 1u : 0u;        // carry of t[0] + m * r[0], r[0] = 1
-#pragma unroll
-        for (int j = 1; j < 8; ++j) {
-            c = (uint64_t)m * frc::MOD[j] + t[j] + c;
-            t[j - 1] = (uint32_t)c;
-            c >>= 32;
-        }
-        top += c;
-        t[7] = (uint32_t)top;
-        t8 = (uint32_t)(top >> 32);
+    for (int i = 0; i < 9; ++i) {
+        const int bit = 29 * i, w = bit >> 5, sh = bit & 31;
+        uint32_t x = a.v[w] >> sh;
+        if (sh > 3 && w + 1 < 8) x |= a.v[w + 1] << (32 - sh);
+        o.v[i] = x & frc::M29;
     }
-    // t < 2r < 2^256, so t8 == 0 here
+    return o;
+}
+
+// normal 9 x 29 with value < 2^256 -> 8 x 32; word w starts at bit 3w of limb w
+FR_HD Fr fr_pack(const F9& t) {
     Fr o;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o.v[i] = t[i];
-    return fr_cond_sub(o);
+    for (int w = 0; w < 8; ++w) o.v[w] = (t.v[w] >> (3 * w)) | (t.v[w + 1] << (29 - 3 * w));
+    return o;
+}
+
+// Montgomery product of two values in 29-bit limbs: (a * b + m * r) / 2^261.
+// Limb bounds: (max limb of a) * (max limb of b) < 2^60.6.  The result is normal and
+// below a * b / 2^261 + r.
+FR_HD F9 f9_mul(const F9& a, const F9& b) {
+    uint64_t acc = 0;
+    uint32_t m[9];
+    F9 t;
+#pragma unroll
+    for (int k = 0; k < 17; ++k) {
+        const int lo_i = k < 9 ? 0 : k - 8, hi_i = k < 9 ? k : 8;
+#pragma unroll
+        for (int i = lo_i; i <= hi_i; ++i) acc += (uint64_t)a.v[i] * b.v[k - i];
+#pragma unroll
+        for (int i = lo_i; i <= hi_i; ++i)
+            if (k - i >= 1) acc += (uint64_t)m[i] * frc::MOD9[k - i];
+        if (k < 9) {
+            m[k] = (0u - (uint32_t)acc) & frc::M29;   // m = -t * r^{-1} mod 2^29, r^{-1} = 1
+            acc += m[k];                              // m * r[0], r[0] = 1: the low 29 bits vanish
+        } else {
+            t.v[k - 9] = (uint32_t)acc & frc::M29;
+        }
+        acc >>= 29;
+    }
+    t.v[8] = (uint32_t)acc;
+    return t;
+}
+
+// t - r if t >= r else t, for a normal t < 2r
+FR_HD F9 f9_cond_sub(const F9& t) {
+    F9 d;
+    int32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+        int32_t x = (int32_t)t.v[i] - (int32_t)frc::MOD9[i] + c;
+        d.v[i] = (uint32_t)x & frc::M29;
+        c = x >> 29;   // 0 or -1
+    }
+    // the top limb holds the sign: after the loop c < 0 iff t < r
+    F9 o;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) o.v[i] = c < 0 ? t.v[i] : d.v[i];
+    return o;
+}
+
+// Montgomery product a * b / 2^261 mod r, fully reduced.
+// Requires a < r; b may be any 256-bit value (a * b / 2^261 + r < 2r), which is
+// what the wide reduction of hash output relies on.
+FR_HD Fr fr_mul(const Fr& a, const Fr& b) {
+    return fr_pack(f9_cond_sub(f9_mul(fr_unpack(a), fr_unpack(b))));
 }
 
 FR_HD Fr fr_sqr(const Fr& a) { return fr_mul(a, a); }
@@ -187,7 +237,7 @@ FR_HD Fr fr_from_u32(uint32_t x) {
 
 // lo + 2^256 * hi mod r, both halves arbitrary 256-bit values, to Montgomery form
 FR_HD Fr fr_from_wide(const Fr& lo, const Fr& hi) {
-    return fr_add(fr_mul(fr_const(frc::R2), lo), fr_mul(fr_const(frc::R3), hi));
+    return fr_add(fr_mul(fr_const(frc::R2), lo), fr_mul(fr_const(frc::W3), hi));
 }
 
 // a^e for a 256-bit exponent given as limbs (host-side constants only)

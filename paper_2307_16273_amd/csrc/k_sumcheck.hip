@@ -78,8 +78,10 @@ struct FinArgs {
 // draws the round's challenge and sets the next claim g_t(v_t).
 __global__ __launch_bounds__(ZK_BLOCK) void k_sc_finalise(FinArgs a) {
     __shared__ uint32_t red[64];
-    __shared__ uint8_t lds[TS_LDS_BYTES];
-    __shared__ Fr g[ZK_MAX_EVALS];
+    __shared__ TsShared S;
+    __shared__ Fr g[ZK_MAX_EVALS + 1];
+    DevState* st = a.st;
+    block_ts_load(S, st);
     for (int x = 0; x < a.npts; ++x) {
         Fr s = fr_zero();
         for (int b = threadIdx.x; b < a.nblk; b += blockDim.x)
@@ -87,14 +89,14 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_finalise(FinArgs a) {
         s = block_sum(s, red);
         if (threadIdx.x == 0) g[x] = s;
     }
-    if (threadIdx.x == 0) {
-        DevState* st = a.st;
-        if (a.first) {
-            Fr c0 = fr_add(g[0], g[1]);
-            dev_absorb_frs(st, "c", 1, &c0, 1, st->proof + a.claim_off, lds);
-        }
-        dev_finalise_round(st, g, a.npts, a.proof_off, a.chal_idx, lds);
+    __syncthreads();
+    if (a.first) {
+        if (threadIdx.x == 0) g[ZK_MAX_EVALS] = fr_add(g[0], g[1]);
+        __syncthreads();
+        block_absorb_frs(S, 'c', &g[ZK_MAX_EVALS], 1, (uint32_t*)(st->proof + a.claim_off));
     }
+    block_finalise_round(S, st, g, a.npts, a.proof_off, a.chal_idx);
+    block_ts_store(S, st);
 }
 
 void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_t proof_off, int first,
@@ -123,12 +125,13 @@ struct FinishArgs {
     uint32_t claim_off;
 };
 
-__global__ void k_sc_finish(FinishArgs a) {
-    __shared__ uint8_t lds[TS_LDS_BYTES];
-    if (threadIdx.x != 0) return;
+__global__ __launch_bounds__(64) void k_sc_finish(FinishArgs a) {
+    __shared__ TsShared S;
+    __shared__ Fr f[4];
     DevState* st = a.st;
-    Fr f[3];
-    for (int k = 0; k < a.K; ++k) {
+    block_ts_load(S, st);
+    if (threadIdx.x < (unsigned)a.K) {
+        const int k = threadIdx.x;
         Fr lo = tab_ld(a.src[k], 0);
         if (a.fold) {
             Fr hi = tab_ld(a.src[k], 1);
@@ -137,13 +140,19 @@ __global__ void k_sc_finish(FinishArgs a) {
         f[k] = lo;
         st->scal[a.scal_base + k] = lo;
     }
+    __syncthreads();
     if (a.absorb_claim) {
-        Fr c0 = f[0];
-        for (int k = 1; k < a.K; ++k) c0 = fr_mul(c0, f[k]);
-        st->claim = c0;
-        dev_absorb_frs(st, "c", 1, &c0, 1, st->proof + a.claim_off, lds);
+        if (threadIdx.x == 0) {
+            Fr c0 = f[0];
+            for (int k = 1; k < a.K; ++k) c0 = fr_mul(c0, f[k]);
+            st->claim = c0;
+            f[3] = c0;
+        }
+        __syncthreads();
+        block_absorb_frs(S, 'c', &f[3], 1, (uint32_t*)(st->proof + a.claim_off));
     }
-    dev_absorb_frs(st, "f", 1, f, a.K, st->proof + a.finals_off, lds);
+    block_absorb_frs(S, 'f', f, a.K, (uint32_t*)(st->proof + a.finals_off));
+    block_ts_store(S, st);
 }
 
 template <int K>
@@ -205,37 +214,14 @@ int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, const FrTab* wor
 }
 
 // ---- transcript-only kernels -----------------------------------------------------
-__global__ void k_draw(DevState* st, int base, int count) {
-    if (threadIdx.x != 0) return;
-    for (int i = 0; i < count; ++i) dev_challenge(st, base + i);
+__global__ __launch_bounds__(ZK_BLOCK) void k_draw(DevState* st, int base, int count) {
+    __shared__ TsShared S;
+    block_ts_load(S, st);
+    block_challenges(S, st, base, count);
+    block_ts_store(S, st);
 }
 
 void zk_launch_draw(zkdl_ctx* ctx, int chal_base, int count) {
     if (count <= 0) return;
-    hipLaunchKernelGGL(k_draw, dim3(1), dim3(64), 0, ctx->stream, ctx->dev, chal_base, count);
-}
-
-struct LabelArg {
-    char s[32];
-    uint32_t len;
-};
-
-__global__ void k_absorb_scal(DevState* st, LabelArg label, int scal_base, int count, uint32_t proof_off,
-                              int write_proof) {
-    __shared__ uint8_t lds[TS_LDS_BYTES];
-    if (threadIdx.x != 0) return;
-    dev_absorb_frs(st, label.s, label.len, &st->scal[scal_base], count,
-                   write_proof ? st->proof + proof_off : nullptr, lds);
-}
-
-void zk_launch_absorb_scal(zkdl_ctx* ctx, const char* label, int scal_base, int count,
-                           size_t proof_off) {
-    LabelArg la;
-    la.len = 0;
-    while (label[la.len] && la.len < 31) {
-        la.s[la.len] = label[la.len];
-        ++la.len;
-    }
-    hipLaunchKernelGGL(k_absorb_scal, dim3(1), dim3(64), 0, ctx->stream, ctx->dev, la, scal_base, count,
-                       (uint32_t)proof_off, 1);
+    hipLaunchKernelGGL(k_draw, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, chal_base, count);
 }

@@ -105,20 +105,24 @@ struct ClaimsArgs {
 // input claims -> proof and transcript; draw r, r'; weights; combined claim
 __global__ __launch_bounds__(ZK_BLOCK) void k_zk_claims(ClaimsArgs a) {
     __shared__ uint32_t red[64];
-    __shared__ uint8_t lds[TS_LDS_BYTES];
+    __shared__ TsShared S;
     __shared__ Fr c[4];
+    DevState* st = a.st;
+    block_ts_load(S, st);
     for (int q = 0; q < 4; ++q) {
         Fr s = fr_zero();
         for (int b = threadIdx.x; b < a.nblk; b += blockDim.x) s = fr_add(s, a.part[(uint64_t)b * 4 + q]);
         s = block_sum(s, red);
         if (threadIdx.x == 0) c[q] = s;
     }
+    __syncthreads();
+    if (threadIdx.x < 4) st->scal[threadIdx.x] = c[threadIdx.x];
+    block_absorb_frs(S, 'c', c, 4, (uint32_t*)(st->proof + a.claims_off));
+    block_challenges(S, st, a.chal_r, 2);   // r, r': one draw
+    block_ts_store(S, st);
     if (threadIdx.x != 0) return;
-    DevState* st = a.st;
-    for (int q = 0; q < 4; ++q) st->scal[q] = c[q];
-    dev_absorb_frs(st, "c", 1, c, 4, st->proof + a.claims_off, lds);
-    Fr r = dev_challenge(st, a.chal_r);
-    Fr rp = dev_challenge(st, a.chal_r + 1);
+    Fr r = st->chal[a.chal_r];
+    Fr rp = st->chal[a.chal_r + 1];
     Fr r2 = fr_sqr(r);
     st->weights[0] = r2;
     st->weights[1] = r;
@@ -128,7 +132,9 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_claims(ClaimsArgs a) {
     Fr claim = fr_zero();
     for (int q = 0; q < 4; ++q) claim = fr_add(claim, fr_mul(st->weights[q], c[q]));
     st->claim = claim;
-    ts::fr_to_le(claim, st->proof + a.claim0_off);
+    Fr plain = fr_from_mont(claim);
+    uint32_t* dst = (uint32_t*)(st->proof + a.claim0_off);
+    for (int l = 0; l < 8; ++l) dst[l] = plain.v[l];
 }
 
 // the equation weights go into the four beta tables: beta_Z *= r^2, beta_A *= r, ...
@@ -403,15 +409,16 @@ __device__ __forceinline__ Fr tail_block_sum(Fr x, uint32_t* red) { return block
 
 __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
     __shared__ uint32_t red[64];
-    __shared__ uint8_t lds[TS_LDS_BYTES];
+    __shared__ TsShared TS;
     __shared__ Fr A0[64], A1[64], S[64], SP[64], BJ[64];   // tables over j
     __shared__ Fr M[128], E[128];                           // merge tables over (k, j)
     __shared__ Fr sc[LIN_TABLES];
     __shared__ Fr g[4];
-    __shared__ Fr vsh;
+    __shared__ Fr fin[3];
     __shared__ Fr rho[3];
     const int tid = threadIdx.x;
     DevState* st = a.st;
+    block_ts_load(TS, st);
     const int J = 1 << a.lj, nbits = a.q_bits + a.r_bits;
     const Fr one = fr_one();
     Fr vlast = fr_zero();
@@ -502,11 +509,9 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
             Fr s = block_sum(f[x], red);
             if (tid == 0) g[x] = s;
         }
-        if (tid == 0)
-            vsh = dev_finalise_round(st, g, 4, a.rounds_off + (uint32_t)(a.li + t) * 128,
-                                     a.chal_v + a.li + t, lds);
         __syncthreads();
-        Fr v = vsh;
+        Fr v = block_finalise_round(TS, st, g, 4, a.rounds_off + (uint32_t)(a.li + t) * 128,
+                                    a.chal_v + a.li + t);
         if (tid < half) {
             A0[tid] = fr_add(A0[tid], fr_mul(v, fr_sub(A0[tid + half], A0[tid])));
             A1[tid] = fr_add(A1[tid], fr_mul(v, fr_sub(A1[tid + half], A1[tid])));
@@ -519,13 +524,22 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
     }
     // finals: aux~(0, v, wbar), aux~(1, v, wbar), aux~(0, v, Q+R-1) = 1 - (1 - sign)(v)
     if (tid == 0) {
-        Fr fin[3] = {A0[0], A1[0], fr_sub(one, sc[T_NS])};
+        fin[0] = A0[0];
+        fin[1] = A1[0];
+        fin[2] = fr_sub(one, sc[T_NS]);
         for (int k = 0; k < 3; ++k) st->scal[4 + k] = fin[k];
-        dev_absorb_frs(st, "f", 1, fin, 3, st->proof + a.finals_off, lds);
-        for (int k = 0; k < 3; ++k) rho[k] = dev_challenge(st, a.chal_rho + k);
+    }
+    __syncthreads();
+    block_absorb_frs(TS, 'f', fin, 3, (uint32_t*)(st->proof + a.finals_off));
+    block_challenges(TS, st, a.chal_rho, 3);   // rho0..2: one vector draw
+    if (tid < 3) rho[tid] = st->chal[a.chal_rho + tid];
+    __syncthreads();
+    if (tid == 0) {
         Fr mc = fr_add(fr_add(fr_mul(rho[0], fin[0]), fr_mul(rho[1], fin[1])), fr_mul(rho[2], fin[2]));
         st->claim = mc;
-        ts::fr_to_le(mc, st->proof + a.merge_claim_off);
+        Fr plain = fr_from_mont(mc);
+        uint32_t* dst = (uint32_t*)(st->proof + a.merge_claim_off);
+        for (int l = 0; l < 8; ++l) dst[l] = plain.v[l];
     }
     // beta~(wbar, .) over j, built in place from the last coordinate upwards (into E[0..J))
     if (tid == 0) E[0] = one;
@@ -593,10 +607,8 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
             Fr s = block_sum(f[x], red);
             if (tid == 0) g[x] = s;
         }
-        if (tid == 0)
-            vsh = dev_finalise_round(st, g, 3, a.merge_rounds_off + (uint32_t)t * 96, a.chal_rho + 3 + t, lds);
         __syncthreads();
-        Fr v = vsh;
+        Fr v = block_finalise_round(TS, st, g, 3, a.merge_rounds_off + (uint32_t)t * 96, a.chal_rho + 3 + t);
         if (tid < half) {
             M[tid] = fr_add(M[tid], fr_mul(v, fr_sub(M[tid + half], M[tid])));
             E[tid] = fr_add(E[tid], fr_mul(v, fr_sub(E[tid + half], E[tid])));
@@ -605,11 +617,14 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
         cur = half;
     }
     if (tid == 0) {
-        Fr fin[2] = {M[0], E[0]};
+        fin[0] = M[0];
+        fin[1] = E[0];
         st->scal[7] = fin[0];
         st->scal[8] = fin[1];
-        dev_absorb_frs(st, "f", 1, fin, 2, st->proof + a.merge_finals_off, lds);
     }
+    __syncthreads();
+    block_absorb_frs(TS, 'f', fin, 2, (uint32_t*)(st->proof + a.merge_finals_off));
+    block_ts_store(TS, st);
 }
 
 unsigned blocks_for(uint64_t n, unsigned cap) {

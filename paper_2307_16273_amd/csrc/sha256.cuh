@@ -5,8 +5,10 @@
 // polynomial (App. B); the transcript replaces that message by a hash:
 //   state_0          = SHA256("zkdl-mi355x/v1" || u64le(seed))
 //   absorb(label, m) : state <- SHA256(state || u8(|label|) || label || u64le(|m|) || m)
-//   challenge()      : d0 = SHA256(state || 0x00), d1 = SHA256(state || 0x01),
-//                      c = int_le(d0 || d1) mod r, state <- SHA256(state || 0x02)
+//   challenges(n)    : for i < n: d0 = SHA256(state || 0x00 || u32le(i)),
+//                      d1 = SHA256(state || 0x01 || u32le(i)), c_i = int_le(d0 || d1) mod r;
+//                      then state <- SHA256(state || 0x02).  challenge() = challenges(1)[0].
+//                      The n elements of one draw are independent hashes: one per lane.
 #pragma once
 #include <stdint.h>
 #include <hip/hip_runtime.h>
@@ -81,26 +83,47 @@ SHA_HD void digest_inplace(uint8_t* msg, uint32_t len, uint8_t out[32]) {
     }
 }
 
-// SHA256(state || suffix) for a one-byte suffix, from registers only
-SHA_HD void digest_state_suffix(const uint8_t state[32], uint8_t suffix, uint8_t out[32]) {
+// SHA256(state || suffix [|| u32le(idx)]) from registers only; state and result as
+// the eight big-endian words of the digest
+SHA_HD void digest_state_suffix_w(const uint32_t st[8], uint32_t suffix, bool with_idx, uint32_t idx,
+                                  uint32_t out[8]) {
     uint32_t w[16];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-        w[i] = ((uint32_t)state[4 * i] << 24) | ((uint32_t)state[4 * i + 1] << 16) |
-               ((uint32_t)state[4 * i + 2] << 8) | state[4 * i + 3];
-    w[8] = ((uint32_t)suffix << 24) | 0x00800000u;
+    for (int i = 0; i < 8; ++i) w[i] = st[i];
+    if (with_idx) {
+        w[8] = (suffix << 24) | ((idx & 0xffu) << 16) | (((idx >> 8) & 0xffu) << 8) | ((idx >> 16) & 0xffu);
+        w[9] = ((idx >> 24) << 24) | 0x00800000u;
+    } else {
+        w[8] = (suffix << 24) | 0x00800000u;
+        w[9] = 0;
+    }
 #pragma unroll
-    for (int i = 9; i < 15; ++i) w[i] = 0;
-    w[15] = 33 * 8;
+    for (int i = 10; i < 15; ++i) w[i] = 0;
+    w[15] = with_idx ? 37 * 8 : 33 * 8;
     uint32_t h[8] = {0x6a09e667, 0xbb67ae85, 0x3c6ef372, 0xa54ff53a,
                      0x510e527f, 0x9b05688c, 0x1f83d9ab, 0x5be0cd19};
     compress(h, w);
 #pragma unroll
+    for (int i = 0; i < 8; ++i) out[i] = h[i];
+}
+
+SHA_HD uint32_t bswap32(uint32_t x) {
+    return (x >> 24) | ((x >> 8) & 0xff00u) | ((x << 8) & 0xff0000u) | (x << 24);
+}
+
+SHA_HD void bytes_to_words(const uint8_t b[32], uint32_t w[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        w[i] = ((uint32_t)b[4 * i] << 24) | ((uint32_t)b[4 * i + 1] << 16) | ((uint32_t)b[4 * i + 2] << 8) | b[4 * i + 3];
+}
+
+SHA_HD void words_to_bytes(const uint32_t w[8], uint8_t b[32]) {
+#pragma unroll
     for (int i = 0; i < 8; ++i) {
-        out[4 * i] = (uint8_t)(h[i] >> 24);
-        out[4 * i + 1] = (uint8_t)(h[i] >> 16);
-        out[4 * i + 2] = (uint8_t)(h[i] >> 8);
-        out[4 * i + 3] = (uint8_t)h[i];
+        b[4 * i] = (uint8_t)(w[i] >> 24);
+        b[4 * i + 1] = (uint8_t)(w[i] >> 16);
+        b[4 * i + 2] = (uint8_t)(w[i] >> 8);
+        b[4 * i + 3] = (uint8_t)w[i];
     }
 }
 
@@ -126,23 +149,28 @@ SHA_HD void absorb(uint8_t state[32], const char* label, uint32_t label_len, con
     sha::digest_inplace(buf, p, state);
 }
 
-// draw one challenge; returns it in Montgomery form and, if le_out != nullptr,
-// as 32 canonical little-endian bytes
-SHA_HD Fr challenge(uint8_t state[32], uint8_t* le_out) {
-    uint8_t d0[32], d1[32], nx[32];
-    sha::digest_state_suffix(state, 0x00, d0);
-    sha::digest_state_suffix(state, 0x01, d1);
-    sha::digest_state_suffix(state, 0x02, nx);
+// element i of a draw from the state given as big-endian words (Montgomery form)
+SHA_HD Fr challenge_elem_w(const uint32_t st[8], uint32_t idx) {
+    uint32_t d0[8], d1[8];
+    sha::digest_state_suffix_w(st, 0x00, true, idx, d0);
+    sha::digest_state_suffix_w(st, 0x01, true, idx, d1);
     Fr lo, hi;
 #pragma unroll
     for (int l = 0; l < 8; ++l) {
-        lo.v[l] = d0[4 * l] | ((uint32_t)d0[4 * l + 1] << 8) | ((uint32_t)d0[4 * l + 2] << 16) |
-                  ((uint32_t)d0[4 * l + 3] << 24);
-        hi.v[l] = d1[4 * l] | ((uint32_t)d1[4 * l + 1] << 8) | ((uint32_t)d1[4 * l + 2] << 16) |
-                  ((uint32_t)d1[4 * l + 3] << 24);
+        lo.v[l] = sha::bswap32(d0[l]);   // little-endian limbs of the digest bytes
+        hi.v[l] = sha::bswap32(d1[l]);
     }
-    for (int i = 0; i < 32; ++i) state[i] = nx[i];
-    Fr c = fr_from_wide(lo, hi);
+    return fr_from_wide(lo, hi);
+}
+
+// draw one challenge; returns it in Montgomery form and, if le_out != nullptr,
+// as 32 canonical little-endian bytes
+SHA_HD Fr challenge(uint8_t state[32], uint8_t* le_out) {
+    uint32_t st[8], nx[8];
+    sha::bytes_to_words(state, st);
+    Fr c = challenge_elem_w(st, 0);
+    sha::digest_state_suffix_w(st, 0x02, false, 0, nx);
+    sha::words_to_bytes(nx, state);
     if (le_out) {
         Fr plain = fr_from_mont(c);
 #pragma unroll

@@ -18,7 +18,7 @@ constexpr int ZK_BLOCK = 256;
 
 // Device-resident state of the call in flight.
 struct DevState {
-    uint8_t ts_state[32];   // transcript state
+    uint32_t ts_state[8];   // transcript state: the SHA-256 digest as big-endian words
     uint32_t err;           // bit 0: zkReLU input out of range
     uint32_t pad0[7];
     Fr claim;               // claim of the running sumcheck (Montgomery)
@@ -109,8 +109,6 @@ struct ScTables {
 int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, const FrTab* work, int d,
                         int finals_scal_base);
 void zk_launch_draw(zkdl_ctx* ctx, int chal_base, int count);
-void zk_launch_absorb_scal(zkdl_ctx* ctx, const char* label, int scal_base, int count,
-                           size_t proof_off);
 
 // ---- k_zkrelu.hip ----------------------------------------------------------------
 int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q, int R);

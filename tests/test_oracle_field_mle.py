@@ -49,10 +49,21 @@ def test_transcript_format():
     s1 = hashlib.sha256(s0 + b"\x01g" + struct.pack("<Q", 2) + b"\x01\x02").digest()
     assert t.digest() == s1
     c = t.challenge()
-    wide = hashlib.sha256(s1 + b"\x00").digest() + hashlib.sha256(s1 + b"\x01").digest()
+    z4 = struct.pack("<I", 0)
+    wide = hashlib.sha256(s1 + b"\x00" + z4).digest() + hashlib.sha256(s1 + b"\x01" + z4).digest()
     assert c == int.from_bytes(wide, "little") % R_MOD
-    assert t.digest() == hashlib.sha256(s1 + b"\x02").digest()
+    s2 = hashlib.sha256(s1 + b"\x02").digest()
+    assert t.digest() == s2
     assert t.challenge() != c
+    # a vector draw: index-derived elements, one state update
+    t2 = Transcript(9)
+    t2.absorb(b"g", b"\x01\x02")
+    vec = t2.challenges_vec(3)
+    assert vec[0] == c and len(set(vec)) == 3 and t2.digest() == s2
+    i2 = struct.pack("<I", 2)
+    wide = hashlib.sha256(s1 + b"\x00" + i2).digest() + hashlib.sha256(s1 + b"\x01" + i2).digest()
+    assert vec[2] == int.from_bytes(wide, "little") % R_MOD
+    assert t2.challenges_vec(0) == [] and t2.digest() == s2
 
 
 def test_beta_table_boolean_points_are_one_hot_msb_first():
