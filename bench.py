@@ -3,24 +3,69 @@
 A step is one pass of the kernel micro-benchmark workload: a degree-3 sumcheck
 over the product of three tables of 2^24 uniform Fr elements (24 rounds) plus
 the partial evaluation of a 4096 x 4096 uniform Fr matrix at a random row point.
-Prints one JSON line (see the design doc for the fields).
+Inputs are resident in HBM before the timed region.  Prints one JSON line; the
+fields are described in the design doc.
 """
 import argparse
 import json
+import os
+import re
 import sys
 import time
 
 import numpy as np
 
+ROOT = os.path.dirname(os.path.abspath(__file__))
+HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E, published
+# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one 32x32+64-bit multiply-add per lane and clock
+MAD_PEAK_T = 256 * 4 * 16 * 2.4e9 / 1e12
+MADS_PER_MODMUL = 153                       # 81 operand + 72 reduction products on 9 x 29-bit limbs
+MODMUL_PER_PAIR_K3 = 14                     # fused round, K = 3: 6 folds + 8 products
+
+
+def traffic_from_profiles():
+    """Measured HBM bytes per launch of the fused round kernel, if a counter summary is committed."""
+    path = os.path.join(ROOT, "profiles", "k_sc_round_fused_microbench_pmc.txt")
+    try:
+        m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(log2_size):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload (one core)."""
+    from oracle import protocols as P
+    from oracle.field import fr_array_from_le
+    from oracle.mle import partial_eval
+    from oracle.transcript import Transcript as OT
+    from workloads import uniform_fr_limbs, CONFIG_SEED
+    n = 1 << log2_size
+    side = 1 << (log2_size // 2)
+    rng = np.random.default_rng(CONFIG_SEED + 2)
+    tabs = [fr_array_from_le(uniform_fr_limbs(rng, n).tobytes(), n) for _ in range(3)]
+    mat = fr_array_from_le(uniform_fr_limbs(rng, side * side).tobytes(), side * side)
+    pt = [int(x) for x in fr_array_from_le(uniform_fr_limbs(rng, log2_size // 2).tobytes(), log2_size // 2)]
+    t0 = time.perf_counter()
+    P.product_prove(tabs, OT(CONFIG_SEED + 2))
+    partial_eval(mat, [side, side], 0, 1, pt)
+    dt = time.perf_counter() - t0
+    return {"value": (3 * n + side * side) / dt, "unit": "Fr elements/s", "cores": 1, "kind": "oracle",
+            "sample": f"same workload at 3 tables of 2^{log2_size} and a {side}x{side} matrix, "
+                      f"{dt:.1f} s of Python-integer oracle on one core"}
+
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--log2-size", type=int, default=24, help="log2 of each sumcheck table (24 = the named workload)")
     ap.add_argument("--no-aggregate", action="store_true", help="skip the 8-layer batch-64 proof timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-log2-size", type=int, default=21)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (a known size for scaling HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -46,6 +91,12 @@ def main():
         zk.sumcheck_product(ctx, tabs, tr)
         zk.mle_partial_eval(ctx, mat, 0, 1, point).free()
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for k in range(args.warmup):
         step(k)
     torch.cuda.synchronize()
@@ -54,9 +105,15 @@ def main():
         step(k)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # the same steps again with HIP events around every kernel, recorded on the library's
+    # stream (two event records per launch would otherwise sit inside the timed region)
+    ctx.profile(True)
+    for k in range(args.steps):
+        step(k)
+    prof = ctx.profile_read()
+    ctx.profile(False, reset=False)
     elems = (3 * n + side * side) * args.steps
 
-    # the two halves on their own
     def timed(fn, reps):
         fn()
         torch.cuda.synchronize()
@@ -67,14 +124,29 @@ def main():
             torch.cuda.synchronize()
             ts.append(time.perf_counter() - a)
         return float(np.median(ts)), float(np.min(ts))
-    sc_med, sc_min = timed(lambda: zk.sumcheck_product(ctx, tabs, zk.Transcript(5)), max(3, args.steps))
-    pe_med, pe_min = timed(lambda: zk.mle_partial_eval(ctx, mat, 0, 1, point).free(), max(3, args.steps))
+    sc_med, sc_min = timed(lambda: zk.sumcheck_product(ctx, tabs, zk.Transcript(5)), 5)
+    pe_med, pe_min = timed(lambda: zk.mle_partial_eval(ctx, mat, 0, 1, point).free(), 5)
 
+    fused = prof["sc_round_fused"]
+    ach = fused["bytes"] / (fused["ms"] * 1e-3) / 1e9 if fused["ms"] > 0 else 0.0
+    pairs = fused["bytes"] / 576.0            # K = 3: 576 algorithmic bytes per pair index
+    mad_rate = pairs * MODMUL_PER_PAIR_K3 * MADS_PER_MODMUL / (fused["ms"] * 1e-3) / 1e12 if fused["ms"] > 0 else 0.0
+    roofline = {
+        "kernel": "k_sc_round<3,true> (fused fold-and-evaluate round)",
+        "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+        "traffic": traffic_from_profiles(),
+        "launches": fused["launches"], "avg_launch_us": 1e3 * fused["ms"] / max(fused["launches"], 1),
+        "algorithmic_bytes_per_launch": fused["bytes"] / max(fused["launches"], 1),
+        "alu": {"achieved": mad_rate, "peak": MAD_PEAK_T, "unit": "Tmad/s", "frac": mad_rate / MAD_PEAK_T},
+        "other_kernels": {k: {"launches": v["launches"], "ms": v["ms"],
+                              "GBps": (v["bytes"] / (v["ms"] * 1e-3) / 1e9 if v["ms"] > 0 else 0.0)}
+                          for k, v in prof.items() if k != "sc_round_fused" and v["launches"]},
+    }
     out = {
         "metric": "Fr elements/s through sumcheck prover; proof ms per batch-64 8-layer step",
         "value": elems / dt, "unit": "Fr elements/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "u32x8 Montgomery (Fr, 255-bit modular integers)",
+        "scaling": "weak", "vs_baseline": None, "dtype": "u32 limbs (Fr, 255-bit modular integers)",
         "data": "synthetic",
         "config": {"workload": f"kernel microbench: degree-3 sumcheck over 3 tables of 2^{d} uniform Fr "
                                f"({d} rounds) + mle_partial_eval of a {side}x{side} Fr matrix at a row point",
@@ -82,6 +154,7 @@ def main():
                    "sumcheck_elems_per_s": 3 * n / sc_med,
                    "partial_eval_ms_median": 1e3 * pe_med, "partial_eval_ms_min": 1e3 * pe_min,
                    "partial_eval_elems_per_s": side * side / pe_med},
+        "roofline": roofline,
     }
     if not args.no_aggregate:
         wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)
@@ -91,7 +164,10 @@ def main():
         ag_med, ag_min = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + 3)), 5)
         out["config"]["proof_ms_batch64_8layer_step"] = 1e3 * ag_med
         out["config"]["proof_ms_batch64_8layer_step_min"] = 1e3 * ag_min
-        out["config"]["paper_context"] = "paper: < 1 s per batch-64 update, 8-layer 10M-parameter net, one A100, whole protocol incl. commitments"
+        out["config"]["paper_context"] = ("paper: < 1 s per batch-64 update, 8-layer 10M-parameter net, one "
+                                          "Tesla A100, whole protocol including commitments (not comparable)")
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_log2_size)
     print(json.dumps(out))
 
 

@@ -178,6 +178,24 @@ typedef struct {
 int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
                     size_t* proof_len, zkdl_fr* points_out, size_t* npoints);
 
+/* ---- per-kernel timing (for callers that measure; paper-independent) -------
+ * While enabled, the launches of the kernel classes below are bracketed by HIP
+ * events on the context's stream; zkdl_ctx_profile_read returns, per class and
+ * since the last reset, the number of launches, the summed event time in ms and
+ * the summed algorithmic bytes (bytes the operation must read and write, not
+ * what the memory system moved). */
+#define ZKDL_PROF_SC_ROUND_FUSED 0 /* fused fold-and-evaluate sumcheck round */
+#define ZKDL_PROF_SC_ROUND_FIRST 1 /* first sumcheck round (evaluate only) */
+#define ZKDL_PROF_PARTIAL_EVAL 2   /* beta-weighted axis contraction */
+#define ZKDL_PROF_ZK_BIN 3         /* zkReLU binarity rounds on the D x (Q+R) tables */
+#define ZKDL_PROF_ZK_LIN 4         /* zkReLU linear rounds on the D-sized tables */
+#define ZKDL_PROF_FINALISE 5       /* per-round transcript step */
+#define ZKDL_PROF_CLASSES 6
+int zkdl_ctx_profile_enable(zkdl_ctx* ctx, int on);
+int zkdl_ctx_profile_reset(zkdl_ctx* ctx);
+int zkdl_ctx_profile_read(zkdl_ctx* ctx, int cls, uint64_t* launches, double* total_ms,
+                          double* total_bytes);
+
 /* ---- host-side self checks (no GPU needed) -------------------------------- */
 /* out = a * b mod r computed by the library's Montgomery code on the host. */
 int zkdl_host_fr_mul(const zkdl_fr* a, const zkdl_fr* b, zkdl_fr* out);

@@ -19,7 +19,11 @@ EXPORTED_SYMBOLS = [
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
     "mle_partial_eval", "sumcheck_product", "sumcheck_matmul", "sumcheck_hadamard",
     "zkrelu_prove", "aggregate_prove", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
+    "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read",
 ]
+
+PROF_CLASSES = {"sc_round_fused": 0, "sc_round_first": 1, "partial_eval": 2, "zk_bin": 3, "zk_lin": 4,
+                "finalise": 5}
 
 
 class ZkdlError(RuntimeError):
@@ -69,6 +73,8 @@ def load_library():
         "zkrelu_prove": [vp, vp, vp, u64, i, i, i, vp, vp, psz, vp, vp, psz],
         "aggregate_prove": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
         "zkdl_host_fr_mul": [vp, vp, vp], "zkdl_selfcheck_constants": [],
+        "zkdl_ctx_profile_enable": [vp, i], "zkdl_ctx_profile_reset": [vp],
+        "zkdl_ctx_profile_read": [vp, i, C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -105,6 +111,23 @@ class Context:
         self.handle = C.c_void_p()
         self.device = device
         _check(lib.zkdl_ctx_create(C.byref(self.handle), device, C.c_void_p(stream)), "zkdl_ctx_create")
+
+    def profile(self, on=True, reset=True):
+        """Per-kernel-class HIP-event timing on this context's stream."""
+        lib = load_library()
+        if reset:
+            _check(lib.zkdl_ctx_profile_reset(self.handle), "zkdl_ctx_profile_reset", self)
+        _check(lib.zkdl_ctx_profile_enable(self.handle, int(on)), "zkdl_ctx_profile_enable", self)
+
+    def profile_read(self):
+        lib = load_library()
+        out = {}
+        for name, cls in PROF_CLASSES.items():
+            n, ms, by = C.c_uint64(), C.c_double(), C.c_double()
+            _check(lib.zkdl_ctx_profile_read(self.handle, cls, C.byref(n), C.byref(ms), C.byref(by)),
+                   "zkdl_ctx_profile_read", self)
+            out[name] = dict(launches=n.value, ms=ms.value, bytes=by.value)
+        return out
 
     def trim(self):
         _check(load_library().zkdl_ctx_trim(self.handle), "zkdl_ctx_trim", self)

@@ -131,6 +131,12 @@ extern "C" int zkdl_ctx_create(zkdl_ctx** out, int device, void* hip_stream) {
     ctx->partials = nullptr;
     ctx->n_chal = 0;
     ctx->proof_len = 0;
+    ctx->prof_on = false;
+    ctx->prof_used = 0;
+    for (int i = 0; i < ZKDL_PROF_CLASSES; ++i) {
+        ctx->prof_ms[i] = ctx->prof_bytes[i] = 0.0;
+        ctx->prof_launches[i] = 0;
+    }
     hipError_t e = hipSetDevice(device);
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->dev, sizeof(DevState));
     if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->host_stage, sizeof(DevState), hipHostMallocDefault);
@@ -168,6 +174,10 @@ extern "C" int zkdl_ctx_create(zkdl_ctx** out, int device, void* hip_stream) {
 extern "C" int zkdl_ctx_destroy(zkdl_ctx* ctx) {
     if (!ctx) return ZKDL_EINVAL;
     (void)hipStreamSynchronize(ctx->stream);
+    for (auto& sp : ctx->prof_spans) {
+        (void)hipEventDestroy(sp.e0);
+        (void)hipEventDestroy(sp.e1);
+    }
     for (auto& kv : ctx->free_blocks) (void)hipFree(kv.second);
     for (auto& kv : ctx->live_blocks) (void)hipFree(kv.first);
     (void)hipFree(ctx->dev);
@@ -178,6 +188,73 @@ extern "C" int zkdl_ctx_destroy(zkdl_ctx* ctx) {
 }
 
 extern "C" int zkdl_last_hip_error(const zkdl_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+// ---------------------------------------------------------------------------
+// per-kernel timing
+// ---------------------------------------------------------------------------
+void zk_prof_begin(zkdl_ctx* ctx, int cls, double bytes) {
+    if (!ctx->prof_on) return;
+    if (ctx->prof_used == ctx->prof_spans.size()) {
+        zkdl_ctx::ProfSpan sp;
+        if (hipEventCreate(&sp.e0) != hipSuccess || hipEventCreate(&sp.e1) != hipSuccess) {
+            ctx->prof_on = false;
+            return;
+        }
+        sp.cls = 0;
+        ctx->prof_spans.push_back(sp);
+    }
+    zkdl_ctx::ProfSpan& sp = ctx->prof_spans[ctx->prof_used];
+    sp.cls = cls;
+    ctx->prof_bytes[cls] += bytes;
+    ctx->prof_launches[cls] += 1;
+    (void)hipEventRecord(sp.e0, ctx->stream);
+}
+
+void zk_prof_end(zkdl_ctx* ctx) {
+    if (!ctx->prof_on) return;
+    (void)hipEventRecord(ctx->prof_spans[ctx->prof_used].e1, ctx->stream);
+    ctx->prof_used += 1;
+}
+
+// folds the pending spans into the per-class totals; the stream must be idle
+static void prof_collect(zkdl_ctx* ctx) {
+    for (size_t i = 0; i < ctx->prof_used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ctx->prof_spans[i].e0, ctx->prof_spans[i].e1) == hipSuccess)
+            ctx->prof_ms[ctx->prof_spans[i].cls] += ms;
+    }
+    ctx->prof_used = 0;
+}
+
+extern "C" int zkdl_ctx_profile_enable(zkdl_ctx* ctx, int on) {
+    if (!ctx) return ZKDL_EINVAL;
+    ZK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    prof_collect(ctx);
+    ctx->prof_on = on != 0;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_ctx_profile_reset(zkdl_ctx* ctx) {
+    if (!ctx) return ZKDL_EINVAL;
+    ZK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->prof_used = 0;
+    for (int i = 0; i < ZKDL_PROF_CLASSES; ++i) {
+        ctx->prof_ms[i] = ctx->prof_bytes[i] = 0.0;
+        ctx->prof_launches[i] = 0;
+    }
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_ctx_profile_read(zkdl_ctx* ctx, int cls, uint64_t* launches, double* total_ms,
+                                     double* total_bytes) {
+    if (!ctx || cls < 0 || cls >= ZKDL_PROF_CLASSES) return ZKDL_EINVAL;
+    ZK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    prof_collect(ctx);
+    if (launches) *launches = ctx->prof_launches[cls];
+    if (total_ms) *total_ms = ctx->prof_ms[cls];
+    if (total_bytes) *total_bytes = ctx->prof_bytes[cls];
+    return ZKDL_OK;
+}
 
 // ---------------------------------------------------------------------------
 // transcript (host)
@@ -450,6 +527,7 @@ static int call_end(zkdl_ctx* ctx, zkdl_transcript* tr, uint8_t* proof, size_t* 
         ZK_HIP(ctx, hipMemcpyAsync(hs + offsetof(DevState, proof), ctx->dev->proof, ctx->proof_len,
                                    hipMemcpyDeviceToHost, ctx->stream));
     ZK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->prof_on) prof_collect(ctx);
     const DevState* h = (const DevState*)hs;
     if (h->err & 1u) return ZKDL_ERANGE;
     sha::words_to_bytes(h->ts_state, tr->state);

@@ -266,9 +266,13 @@ int zk_partial_eval(zkdl_ctx* ctx, int kind, const void* src, uint64_t O, uint64
     } else {
         grid = dim3(grid_for(n_out, 16384), (unsigned)chunks);
     }
+    // algorithmic bytes: the source once, beta once per (outer, inner) tile is cached: count it once, the output
+    const double esz = kind == TK_FR ? 32.0 : kind == TK_I32 ? 4.0 : 8.0;
+    zk_prof_begin(ctx, ZKDL_PROF_PARTIAL_EVAL, esz * (double)O * (double)A * (double)I + 32.0 * (double)A + 32.0 * (double)n_out);
     if (kind == TK_FR) launch_pe<TK_FR>(ctx, inner, p, grid);
     else if (kind == TK_I32) launch_pe<TK_I32>(ctx, inner, p, grid);
     else launch_pe<TK_I64>(ctx, inner, p, grid);
+    zk_prof_end(ctx);
     if (chunks > 1) {
         hipLaunchKernelGGL(k_sum_chunks, dim3(grid_for(n_out)), dim3(ZK_BLOCK), 0, ctx->stream, p.out,
                            n_out, chunks, out);

@@ -110,7 +110,9 @@ void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_
     fa.proof_off = proof_off;
     fa.first = first;
     fa.claim_off = claim_off;
+    zk_prof_begin(ctx, ZKDL_PROF_FINALISE, 32.0 * npts);
     hipLaunchKernelGGL(k_sc_finalise, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+    zk_prof_end(ctx);
 }
 
 struct FinishArgs {
@@ -192,9 +194,13 @@ int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, const FrTab* wor
         ra.part = ctx->partials;
         uint64_t want = (ra.m + ZK_BLOCK - 1) / ZK_BLOCK;
         unsigned grid = (unsigned)(want > ZK_MAX_PART_BLOCKS ? ZK_MAX_PART_BLOCKS : want);
+        // algorithmic bytes: per pair index and table, 2 reads (first round) or 4 reads + 2 writes
+        zk_prof_begin(ctx, fold ? ZKDL_PROF_SC_ROUND_FUSED : ZKDL_PROF_SC_ROUND_FIRST,
+                      (double)K * (fold ? 192.0 : 64.0) * (double)ra.m);
         if (K == 1) launch_round<1>(ctx, fold, ra, grid);
         else if (K == 2) launch_round<2>(ctx, fold, ra, grid);
         else launch_round<3>(ctx, fold, ra, grid);
+        zk_prof_end(ctx);
         zk_launch_finalise(ctx, (int)grid, npts, ctx->n_chal++, rounds_off + (uint32_t)t * npts * 32,
                            t == 0, claim_off);
     }

@@ -760,14 +760,19 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         la.part = ctx->partials;
         la.has_ga = has_ga;
         unsigned nb_lin = blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
+        const double n_lin = has_ga ? 10.0 : 6.0;
+        zk_prof_begin(ctx, ZKDL_PROF_ZK_LIN, n_lin * (t == 0 ? 64.0 : 192.0) * (double)m);
         if (t == 0) hipLaunchKernelGGL(k_zk_lin<false>, dim3(nb_lin), dim3(ZK_BLOCK), 0, ctx->stream, la);
         else hipLaunchKernelGGL(k_zk_lin<true>, dim3(nb_lin), dim3(ZK_BLOCK), 0, ctx->stream, la);
+        zk_prof_end(ctx);
         ba.m = m;
         ba.part = ctx->partials + (uint64_t)nb_lin * 4;
         unsigned nb_bin;
         if (t == 0) {
             nb_bin = blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
+            zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, (has_ga ? 32.0 : 16.0) * (double)m + 64.0 * (double)m);
             hipLaunchKernelGGL(k_zk_bin0, dim3(nb_bin), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            zk_prof_end(ctx);
         } else {
             // few rows: split the columns over more threads
             int jc = nbits;
@@ -776,8 +781,11 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
             unsigned bx = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / chunks);
             ba.jc = jc;
             ba.chal = t >= 2 ? &st->chal[c_v + t - 1] : nullptr;
+            zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN,
+                          (has_ga ? 2.0 : 1.0) * nbits * (t >= 2 ? 192.0 : 64.0) * (double)m + 64.0 * (double)m);
             if (t >= 2) hipLaunchKernelGGL(k_zk_bin<true>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
             else hipLaunchKernelGGL(k_zk_bin<false>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            zk_prof_end(ctx);
             nb_bin = bx * chunks;
         }
         zk_launch_finalise(ctx, (int)(nb_lin + nb_bin), 4, c_v + t, rounds_off + (uint32_t)t * 128, 0, 0);

@@ -57,7 +57,22 @@ struct zkdl_ctx {
     // per-call bookkeeping (host mirrors of device cursors)
     int n_chal;
     size_t proof_len;
+    // optional per-kernel-class timing with HIP events on the context's stream
+    bool prof_on;
+    struct ProfSpan {
+        hipEvent_t e0, e1;
+        int cls;
+    };
+    std::vector<ProfSpan> prof_spans;   // pool; the first prof_used are pending
+    size_t prof_used;
+    double prof_ms[ZKDL_PROF_CLASSES];
+    double prof_bytes[ZKDL_PROF_CLASSES];
+    uint64_t prof_launches[ZKDL_PROF_CLASSES];
 };
+
+// Brackets one kernel launch when profiling is on; `bytes` = algorithmic bytes it moves.
+void zk_prof_begin(zkdl_ctx* ctx, int cls, double bytes);
+void zk_prof_end(zkdl_ctx* ctx);
 
 #define ZK_HIP(ctx, call)                       \
     do {                                        \
