@@ -635,22 +635,18 @@ extern "C" int sumcheck_product(zkdl_ctx* ctx, const zkdl_tensor* const* tables,
     uint32_t hdr[2] = {(uint32_t)K, (uint32_t)d};
     dev_absorb_words(ctx, "sumcheck_product", hdr, 2);
     FrView views[3];
-    FrTab src[3], work[3];
+    FrTab src[3];
     void* wmem = nullptr;
     for (int k = 0; k < K; ++k) views[k].scratch = nullptr;
     for (int k = 0; k < K && rc == ZKDL_OK; ++k) {
         rc = as_fr(ctx, tables[k], &views[k]);
         src[k] = views[k].tab;
     }
-    const uint64_t half = n > 1 ? n / 2 : 1;
     if (rc == ZKDL_OK) {
-        wmem = zk_alloc(ctx, (size_t)K * half * 32);
+        wmem = zk_alloc(ctx, zk_sumcheck_work_bytes(K, d));
         if (!wmem) rc = ZKDL_ENOMEM;
     }
-    if (rc == ZKDL_OK) {
-        for (int k = 0; k < K; ++k) work[k] = make_tab((uint32_t*)wmem + (size_t)k * half * 8, half);
-        rc = zk_sumcheck_product(ctx, K, src, work, d, 0);
-    }
+    if (rc == ZKDL_OK) rc = zk_sumcheck_product(ctx, K, src, wmem, d, 0);
     int ids[3] = {0, 1, 2};
     int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, ids, K, finals);
     zk_free(ctx, wmem);
@@ -689,27 +685,23 @@ static int enqueue_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tenso
     const Fr* chal = ctx->dev->chal;
 
     const uint64_t len = N * D2;
-    const uint64_t half = len > 1 ? len / 2 : 1;
     const uint64_t bmax = D1 > D3 ? D1 : D3;
-    // scratch: beta tables (N, max(D1,D3)), three source tables, one shift temp, three work tables
-    void* mem = zk_alloc(ctx, (N + bmax + 4 * len + 3 * half) * 32);
+    // scratch: beta tables (N, max(D1,D3)), three source tables, one shift temp, the work tables
+    void* mem = zk_alloc(ctx, (N + bmax + 4 * len) * 32 + zk_sumcheck_work_bytes(3, ln + l2));
     if (!mem) return ZKDL_ENOMEM;
     uint32_t* base = (uint32_t*)mem;
     FrTab bw = make_tab(base, N);
     base += 8 * N;
     FrTab bu = make_tab(base, bmax);
     base += 8 * bmax;
-    FrTab src[3], work[3];
+    FrTab src[3];
     for (int k = 0; k < 3; ++k) {
         src[k] = make_tab(base, len);
         base += 8 * len;
     }
     FrTab tmp = make_tab(base, len);
     base += 8 * len;
-    for (int k = 0; k < 3; ++k) {
-        work[k] = make_tab(base, half);
-        base += 8 * half;
-    }
+    void* work = base;
     int rc = zk_build_beta(ctx, chal + cw, ln, bw);
     if (rc == ZKDL_OK) zk_launch_broadcast_rows(ctx, bw, N, D2, src[0]);
     // T0[n, i] = X0~(n, u0, i): bind the D1 axis of op(X0)
@@ -771,8 +763,7 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
     ctx->n_chal = d;
     FrView v0, v1;
     v0.scratch = v1.scratch = nullptr;
-    const uint64_t half = n > 1 ? n / 2 : 1;
-    void* mem = zk_alloc(ctx, (n + 3 * half) * 32);
+    void* mem = zk_alloc(ctx, n * 32 + zk_sumcheck_work_bytes(3, d));
     if (!mem) rc = ZKDL_ENOMEM;
     if (rc == ZKDL_OK) rc = as_fr(ctx, X0, &v0);
     if (rc == ZKDL_OK) rc = as_fr(ctx, X1, &v1);
@@ -780,9 +771,7 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
         FrTab beta = make_tab(mem, n);
         rc = zk_build_beta(ctx, ctx->dev->chal, d, beta);
         FrTab src[3] = {beta, v0.tab, v1.tab};
-        FrTab work[3];
-        for (int k = 0; k < 3; ++k) work[k] = make_tab((uint32_t*)mem + 8 * (n + k * half), half);
-        if (rc == ZKDL_OK) rc = zk_sumcheck_product(ctx, 3, src, work, d, 0);
+        if (rc == ZKDL_OK) rc = zk_sumcheck_product(ctx, 3, src, (uint32_t*)mem + 8 * n, d, 0);
     }
     zkdl_fr tmp[3];
     int ids[3] = {0, 1, 2};

@@ -93,16 +93,16 @@ __device__ inline void block_absorb1(TsShared& S, char label, int count) {
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        uint32_t h[8] = {0x6a09e667, 0xbb67ae85, 0x3c6ef372, 0xa54ff53a,
-                         0x510e527f, 0x9b05688c, 0x1f83d9ab, 0x5be0cd19};
-        for (uint32_t off = 0; off < padded / 4; off += 16) {
-            uint32_t w[16];
+        sha::Words8 h = sha::iv_words();
+        const uint32_t nblocks = padded / 64;
+        for (uint32_t blk = 0; blk < nblocks; ++blk) {
+            sha::Words16 w;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) w[i] = S.msg[off + i];
-            sha::compress(h, w);
+            for (int i = 0; i < 16; ++i) w.v[i] = S.msg[16 * blk + i];
+            h = sha::compress_ni(h, w);
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) S.state[i] = h[i];
+        for (int i = 0; i < 8; ++i) S.state[i] = h.v[i];
     }
     __syncthreads();
 }
@@ -112,7 +112,7 @@ __device__ inline void block_absorb1(TsShared& S, char label, int count) {
 __device__ inline void block_absorb_frs(TsShared& S, char label, const Fr* vals, int count,
                                         uint32_t* proof_dst) {
     if (threadIdx.x < (unsigned)count) {
-        Fr plain = fr_from_mont(vals[threadIdx.x]);
+        Fr plain = fr_from_mont_ni(vals[threadIdx.x]);
 #pragma unroll
         for (int l = 0; l < 8; ++l) {
             S.canon[threadIdx.x][l] = plain.v[l];
@@ -132,13 +132,14 @@ __device__ inline void block_challenges(TsShared& S, DevState* st, int base, int
         const bool last = c0 + n >= count;
         const int jobs = 2 * n + (last ? 1 : 0);
         for (int t = threadIdx.x; t < jobs; t += blockDim.x) {
-            uint32_t stw[8], out[8];
+            uint32_t stw[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) stw[i] = S.state[i];
-            if (t < 2 * n) sha::digest_state_suffix_w(stw, (uint32_t)(t & 1), true, (uint32_t)(c0 + (t >> 1)), out);
-            else sha::digest_state_suffix_w(stw, 2u, false, 0u, out);
+            const bool elem = t < 2 * n;
+            sha::Words8 out = sha::digest_state_suffix_ni(stw, elem ? (uint32_t)(t & 1) : 2u, elem,
+                                                          elem ? (uint32_t)(c0 + (t >> 1)) : 0u);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) S.dig[t][i] = out[i];
+            for (int i = 0; i < 8; ++i) S.dig[t][i] = out.v[i];
         }
         __syncthreads();
         // wide reduction: one lane per half, then one lane per element
@@ -146,7 +147,7 @@ __device__ inline void block_challenges(TsShared& S, DevState* st, int base, int
             Fr x;
 #pragma unroll
             for (int l = 0; l < 8; ++l) x.v[l] = sha::bswap32(S.dig[t][l]);
-            Fr m = fr_mul(fr_const((t & 1) ? frc::W3 : frc::R2), x);
+            Fr m = fr_mul_ni(fr_const((t & 1) ? frc::W3 : frc::R2), x);
 #pragma unroll
             for (int l = 0; l < 8; ++l) S.dig[t][l] = m.v[l];
         }
@@ -161,7 +162,7 @@ __device__ inline void block_challenges(TsShared& S, DevState* st, int base, int
             Fr c = fr_add(lo, hi);
             st->chal[base + c0 + t] = c;
             if (c0 + t == 0) S.v = c;
-            Fr plain = fr_from_mont(c);
+            Fr plain = fr_from_mont_ni(c);
             uint32_t* le = (uint32_t*)(st->chal_le + 32 * (size_t)(base + c0 + t));
 #pragma unroll
             for (int l = 0; l < 8; ++l) le[l] = plain.v[l];
@@ -172,47 +173,147 @@ __device__ inline void block_challenges(TsShared& S, DevState* st, int base, int
     }
 }
 
-// g (LDS, Montgomery, npts = 2..4 values at 0..npts-1) -> value at v, spread over
-// npts lanes: lane k computes g[k] * prod_{j != k} (v - j) / prod_{j != k} (k - j)
-__device__ inline Fr block_lagrange(TsShared& S, const Fr* g, int npts, const Fr& v, const Fr& inv2,
-                                    const Fr& inv6) {
-    __syncthreads();
-    const int k = threadIdx.x;
-    if (k < npts) {
-        const Fr one = fr_one();
-        Fr vj[4];
-        vj[0] = v;
-        for (int j = 1; j < npts; ++j) vj[j] = fr_sub(vj[j - 1], one);
-        Fr num = g[k];
-        for (int j = 0; j < npts; ++j)
-            if (j != k) num = fr_mul(num, vj[j]);
-        // 1 / prod_{j != k} (k - j)
-        Fr coef;
-        bool negate;
-        if (npts == 2) { coef = one; negate = (k == 0); }            // -1, 1
-        else if (npts == 3) { coef = (k == 1) ? one : inv2; negate = (k == 1); }   // 1/2, -1, 1/2
-        else { coef = (k == 0 || k == 3) ? inv6 : inv2; negate = (k == 0 || k == 2); }  // -1/6, 1/2, -1/2, 1/6
-        num = fr_mul(num, coef);
-        S.tmp[k] = negate ? fr_neg(num) : num;
-    }
-    __syncthreads();
-    Fr acc = S.tmp[0];
-    for (int j = 1; j < npts; ++j) acc = fr_add(acc, S.tmp[j]);
-    return acc;   // every thread holds the value
-}
-
-// Closes a round: g_t(0..npts-1) go to the proof and into the transcript, the round's
-// challenge is drawn, the next claim is g_t(v_t).  g in LDS.  Returns v_t.
+// Closes a round: g_t(0..npts-1) (LDS, Montgomery, npts = 2..4) go to the proof and into
+// the transcript, the round's challenge v_t is drawn, the next claim g_t(v_t) is set.
+// Returns v_t to every thread.  Needs blockDim.x >= 128: while wave 0 hashes, wave 1
+// prepares the Lagrange coefficients c_k = g(k) / prod_{j != k} (k - j), and later the
+// canonical form of the challenge, so that after the hash only two dependent
+// multiplications remain:
+//   npts = 4: g(v) = (v-2)(v-3) [c0 (v-1) + c1 v] + v (v-1) [c2 (v-3) + c3 (v-2)]
+//   npts = 3: g(v) = (v-2) [c0 (v-1) + c1 v] + c2 v (v-1)
+//   npts = 2: g(v) = c0 (v-1) + c1 v
 __device__ inline Fr block_finalise_round(TsShared& S, DevState* st, const Fr* g, int npts,
                                           uint32_t proof_off, int chal_idx) {
-    block_absorb_frs(S, 'g', g, npts, (uint32_t*)(st->proof + proof_off));
-    block_challenges(S, st, chal_idx, 1);
-    Fr v = S.v;
-    Fr claim = block_lagrange(S, g, npts, v, st->inv2, st->inv6);
-    if (threadIdx.x == 0) st->claim = claim;
+    const int tid = threadIdx.x;
+    uint32_t* proof_dst = (uint32_t*)(st->proof + proof_off);
+    __syncthreads();
+    // canonical forms (wave 0) | Lagrange coefficients (wave 1)
+    if (tid < npts) {
+        Fr plain = fr_from_mont_ni(g[tid]);
+#pragma unroll
+        for (int l = 0; l < 8; ++l) {
+            S.canon[tid][l] = plain.v[l];
+            proof_dst[8 * tid + l] = plain.v[l];
+        }
+    } else if (tid >= 64 && tid < 64 + npts) {
+        const int k = tid - 64;
+        Fr c = g[k];
+        if (npts == 3) {            // 1/2, -1, 1/2
+            c = (k == 1) ? fr_neg(c) : fr_mul_ni(c, st->inv2);
+        } else if (npts == 4) {     // -1/6, 1/2, -1/2, 1/6
+            c = fr_mul_ni(c, (k == 0 || k == 3) ? st->inv6 : st->inv2);
+            if (k == 0 || k == 2) c = fr_neg(c);
+        } else if (k == 0) {        // -1, 1
+            c = fr_neg(c);
+        }
+        S.tmp[k] = c;
+    }
+    block_absorb1(S, 'g', npts);
+    // challenge hashes: lanes 0, 1 (element), 2 (next state)
+    if (tid < 3) {
+        uint32_t stw[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) stw[i] = S.state[i];
+        const sha::Words8 ow = sha::digest_state_suffix_ni(stw, tid < 2 ? (uint32_t)tid : 2u, tid < 2, 0u);
+        uint32_t out[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = ow.v[i];
+        if (tid < 2) {
+            Fr x;
+#pragma unroll
+            for (int l = 0; l < 8; ++l) x.v[l] = sha::bswap32(out[l]);
+            Fr m = fr_mul_ni(fr_const(tid ? frc::W3 : frc::R2), x);
+#pragma unroll
+            for (int l = 0; l < 8; ++l) S.dig[tid][l] = m.v[l];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) S.dig[2][i] = out[i];
+        }
+    }
+    __syncthreads();
+    Fr lo, hi;
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+        lo.v[l] = S.dig[0][l];
+        hi.v[l] = S.dig[1][l];
+    }
+    const Fr v = fr_add(lo, hi);   // every thread
+    if (tid < 8) S.state[tid] = S.dig[2][tid];
+    if (tid == 0) st->chal[chal_idx] = v;
+    // first level of the Lagrange sum (wave 0, one product per lane) | canonical v (wave 1)
+    const Fr one = fr_one();
+    const Fr v1 = fr_sub(v, one), v2 = fr_sub(v1, one), v3 = fr_sub(v2, one);
+    if (tid < 6) {
+        Fr p = fr_zero();
+        if (npts == 4) {
+            if (tid == 0) p = fr_mul_ni(S.tmp[0], v1);
+            else if (tid == 1) p = fr_mul_ni(S.tmp[1], v);
+            else if (tid == 2) p = fr_mul_ni(S.tmp[2], v3);
+            else if (tid == 3) p = fr_mul_ni(S.tmp[3], v2);
+            else if (tid == 4) p = fr_mul_ni(v2, v3);
+            else p = fr_mul_ni(v, v1);
+        } else if (npts == 3) {
+            if (tid == 0) p = fr_mul_ni(S.tmp[0], v1);
+            else if (tid == 1) p = fr_mul_ni(S.tmp[1], v);
+            else if (tid == 2) p = fr_mul_ni(S.tmp[2], v);
+        } else {
+            if (tid == 0) p = fr_mul_ni(S.tmp[0], v1);
+            else if (tid == 1) p = fr_mul_ni(S.tmp[1], v);
+        }
+#pragma unroll
+        for (int l = 0; l < 8; ++l) S.dig[4 + tid][l] = p.v[l];
+    } else if (tid == 64) {
+        Fr plain = fr_from_mont_ni(v);
+        uint32_t* le = (uint32_t*)(st->chal_le + 32 * (size_t)chal_idx);
+#pragma unroll
+        for (int l = 0; l < 8; ++l) le[l] = plain.v[l];
+    }
+    __syncthreads();
+    if (tid < 2) {
+        Fr q[6];
+#pragma unroll
+        for (int j = 0; j < 6; ++j)
+#pragma unroll
+            for (int l = 0; l < 8; ++l) q[j].v[l] = S.dig[4 + j][l];
+        Fr r;
+        if (npts == 4) r = tid == 0 ? fr_mul_ni(q[4], fr_add(q[0], q[1])) : fr_mul_ni(q[5], fr_add(q[2], q[3]));
+        else if (npts == 3) r = tid == 0 ? fr_mul_ni(v2, fr_add(q[0], q[1])) : fr_mul_ni(q[2], v1);
+        else r = tid == 0 ? fr_add(q[0], q[1]) : fr_zero();
+#pragma unroll
+        for (int l = 0; l < 8; ++l) S.dig[10 + tid][l] = r.v[l];
+    }
+    __syncthreads();
+    if (tid == 0) {
+        Fr r0, r1;
+#pragma unroll
+        for (int l = 0; l < 8; ++l) {
+            r0.v[l] = S.dig[10][l];
+            r1.v[l] = S.dig[11][l];
+        }
+        st->claim = fr_add(r0, r1);
+    }
     return v;
+}
+
+// Sums per-block partial sums part[b * npts + x], b < nblk, into g[x] (LDS): wave x
+// handles evaluation x on its own.  Needs blockDim.x >= 64 * npts.
+__device__ inline void block_reduce_partials(const Fr* part, int nblk, int npts, Fr* g) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (wave < npts) {
+        Fr s = fr_zero();
+        for (int b = lane; b < nblk; b += 64) s = fr_add(s, part[(uint64_t)b * npts + wave]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            Fr y;
+#pragma unroll
+            for (int l = 0; l < 8; ++l) y.v[l] = __shfl_down(s.v[l], off, 64);
+            s = fr_add(s, y);
+        }
+        if (lane == 0) g[wave] = s;
+    }
+    __syncthreads();
 }
 
 // ---- launchers defined in k_sumcheck.hip ----
 void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_t proof_off, int first,
-                        uint32_t claim_off);
+                        uint32_t claim_off, int derive1);

@@ -42,6 +42,11 @@ constexpr uint32_t W3[8] = {0x6dceb833u, 0xb06020dbu, 0xc7e29ae5u, 0xb06c02ccu,
 constexpr uint32_t MOD9[9] = {0x00000001u, 0x1ffffff8u, 0x1f96ffbfu, 0x1b4805ffu, 0x1d80553bu,
                               0x0c0404d0u, 0x1520cce7u, 0x0a6533afu, 0x0073eda7u};
 constexpr uint32_t M29 = 0x1fffffffu;
+// 4r with limbs 0..7 raised by borrowing from the limb above (same value): every
+// limb is >= 2^29 - 1, the top one is top(4r) - 1, so C4R - b is limbwise
+// non-negative for any normal b below 2.6 r
+constexpr uint32_t C4R[9] = {0x20000004u, 0x3fffffdfu, 0x3e5bfefeu, 0x2d2017feu, 0x360154eeu,
+                             0x30101342u, 0x3483339cu, 0x2994cebdu, 0x01cfb69cu};
 }  // namespace frc
 
 // 9 limbs of 29 bits; "normal" means every limb < 2^29
@@ -208,6 +213,84 @@ FR_HD Fr fr_mul(const Fr& a, const Fr& b) {
 
 FR_HD Fr fr_sqr(const Fr& a) { return fr_mul(a, a); }
 
+#if defined(__HIPCC__)
+// Not inlined: for the single-wave transcript kernels, whose instructions run once per
+// launch from a cold instruction cache, one shared copy of the multiplier is fetched once.
+static __device__ __noinline__ Fr fr_mul_ni(Fr a, Fr b) { return fr_mul(a, b); }
+__device__ inline Fr fr_from_mont_ni(const Fr& x) {
+    Fr one = fr_zero();
+    one.v[0] = 1;
+    return fr_mul_ni(x, one);
+}
+#endif
+
+// ---- lazy arithmetic on 29-bit limbs ---------------------------------------------
+// Inside a kernel, values may stay unpacked between operations: limbs are u32 and may
+// exceed 29 bits, values may exceed r.  Each function states what it needs; the
+// invariants used by the kernels are written where they are relied upon.
+
+// limbwise sum: limb and value bounds add
+FR_HD F9 f9_add(const F9& a, const F9& b) {
+    F9 o;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) o.v[i] = a.v[i] + b.v[i];
+    return o;
+}
+
+// a - b + 4r, limbwise and without borrows.  Needs b normal with value < 2.6 r.
+// Limbs of the result are below (limb of a) + 2^30; its value is value(a) - value(b) + 4r.
+FR_HD F9 f9_sub(const F9& a, const F9& b) {
+    F9 o;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) o.v[i] = a.v[i] + (frc::C4R[i] - b.v[i]);
+    return o;
+}
+
+// carry propagation: same value, limbs 0..7 below 2^29
+FR_HD F9 f9_norm(const F9& a) {
+    F9 o;
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t x = a.v[i] + c;
+        o.v[i] = x & frc::M29;
+        c = x >> 29;
+    }
+    o.v[8] = a.v[8] + c;
+    return o;
+}
+
+// carry propagation that also removes q = (top limb >> 23) <= floor(value / 2^255)
+// multiples of r.  Needs limbs below 2^32 and value below 2^263.  The result is
+// normal, congruent to a, non-negative, and below 2.41 r (q misses at most one
+// multiple because of carries still pending below the top limb).
+FR_HD F9 f9_norm_reduce(const F9& a) {
+    F9 o;
+    const int64_t q = (int64_t)(a.v[8] >> 23);
+    int64_t c = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int64_t y = (int64_t)a.v[i] - q * (int64_t)frc::MOD9[i] + c;
+        o.v[i] = (uint32_t)y & frc::M29;
+        c = y >> 29;
+    }
+    o.v[8] = (uint32_t)((int64_t)a.v[8] - q * (int64_t)frc::MOD9[8] + c);
+    return o;
+}
+
+// any lazy value (limbs < 2^32, value < 2^261) -> fully reduced packed form
+FR_HD Fr f9_to_fr(const F9& a) {
+    // multiply by the Montgomery form of 1: the product is congruent to a and below 2r
+    return fr_pack(f9_cond_sub(f9_mul(fr_unpack(fr_const(frc::ONE)), f9_norm(a))));
+}
+
+FR_HD F9 f9_zero() {
+    F9 z;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) z.v[i] = 0;
+    return z;
+}
+
 // plain 256-bit value (any) -> Montgomery form of its residue
 FR_HD Fr fr_to_mont(const Fr& x) { return fr_mul(fr_const(frc::R2), x); }
 
@@ -268,5 +351,20 @@ FR_HD void tab_st(const FrTab& t, uint64_t i, const Fr& x) {
     for (int l = 0; l < 8; ++l) t.p[l * t.ps + i] = x.v[l];
 }
 
-// lo + x * (hi - lo) evaluated along x = 0, 1, 2, 3 needs only additions:
-// e(0) = lo, e(1) = hi, e(k+1) = e(k) + (hi - lo)
+// tables of lazy values: nine planes of u32, limb l of element i at p[l * ps + i]
+struct F9Tab {
+    uint32_t* p;
+    uint64_t ps;
+};
+
+FR_HD F9 f9tab_ld(const F9Tab& t, uint64_t i) {
+    F9 x;
+#pragma unroll
+    for (int l = 0; l < 9; ++l) x.v[l] = t.p[l * t.ps + i];
+    return x;
+}
+
+FR_HD void f9tab_st(const F9Tab& t, uint64_t i, const F9& x) {
+#pragma unroll
+    for (int l = 0; l < 9; ++l) t.p[l * t.ps + i] = x.v[l];
+}

@@ -4,61 +4,100 @@
 #include "dev_common.cuh"
 
 struct RoundArgs {
-    FrTab src[3];
-    FrTab dst[3];
+    FrTab src8[3];     // packed source tables (first round, first fused round)
+    F9Tab work[3];     // lazy 29-bit-limb work tables (written by every fused round)
     uint64_t m;        // half length of the tables this round sums over
-    const Fr* chal;    // challenge of the previous round (FOLD only)
+    const Fr* chal;    // challenge of the previous round (fused rounds)
     Fr* part;          // partial sums: block b, evaluation x at part[b * (K+1) + x]
 };
 
-// Round t of a product of K multilinear tables.
-// FOLD = false: the tables have length 2m; g(x) = sum_b prod_k (lo + x (hi - lo)),
-//               lo = T[b], hi = T[b + m].
-// FOLD = true : the tables still have length 4m; the previous challenge v is bound
-//               first, T'[b] = T[b] + v (T[b + 2m] - T[b]) for b < 2m, the folded
-//               halves are written to dst and the round polynomial is evaluated on
-//               them in the same pass.
-template <int K, bool FOLD>
+// Round t of a product of K multilinear tables (Sec. 2.2).
+// MODE 0 (first round): the tables have length 2m; g(x) = sum_b prod_k (lo + x (hi - lo)),
+//         lo = T[b], hi = T[b + m], for x = 0..K.
+// MODE 1, 2 (fused): the tables still have length 4m; the previous challenge v is bound
+//         first, T'[b] = T[b] + v (T[b + 2m] - T[b]) for b < 2m, the folded halves are
+//         written to the work tables and the round polynomial is evaluated on them in the
+//         same pass.  MODE 1 reads the packed sources, MODE 2 the work tables (in place).
+//         g(1) is not computed: the finaliser takes it from the running claim,
+//         g(1) = claim - g(0).
+//
+// Arithmetic stays in 29-bit limbs from load to the per-thread sums.  Invariants:
+//   stored work values: normal, value < 2.41 r (f9_norm_reduce at the store);
+//   d = hi - lo + 4r has limbs < 2^29 + 2^30; the challenge is normal: product bound holds;
+//   evaluation points: e(2) = hi + dn, e(3) = e(2) + dn with dn = norm(hi - lo + 4r):
+//   limbs < 2^30.6, and every product has one normal factor;
+//   sums are renormalised and reduced after every second addition.
+template <int K, int MODE>
 __global__ __launch_bounds__(ZK_BLOCK) void k_sc_round(RoundArgs a) {
     __shared__ uint32_t red[64];
-    Fr acc[K + 1];
+    constexpr bool FOLD = MODE != 0;
+    F9 acc[K + 1];
 #pragma unroll
-    for (int x = 0; x <= K; ++x) acc[x] = fr_zero();
-    Fr v;
-    if (FOLD) v = *a.chal;
+    for (int x = 0; x <= K; ++x) acc[x] = f9_zero();
+    F9 v = f9_zero();
+    if (FOLD) v = fr_unpack(*a.chal);
     const uint64_t m = a.m;
+    int pending = 0;
     for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
          b += (uint64_t)gridDim.x * blockDim.x) {
-        Fr e[K + 1];
+        F9 prod[K + 1];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            Fr lo, hi;
-            if (FOLD) {
-                Fr t0 = tab_ld(a.src[k], b), t1 = tab_ld(a.src[k], b + m);
-                Fr t2 = tab_ld(a.src[k], b + 2 * m), t3 = tab_ld(a.src[k], b + 3 * m);
-                lo = fr_add(t0, fr_mul(v, fr_sub(t2, t0)));
-                hi = fr_add(t1, fr_mul(v, fr_sub(t3, t1)));
-                tab_st(a.dst[k], b, lo);
-                tab_st(a.dst[k], b + m, hi);
+            F9 lo, hi;
+            if (MODE == 0) {
+                lo = fr_unpack(tab_ld(a.src8[k], b));
+                hi = fr_unpack(tab_ld(a.src8[k], b + m));
             } else {
-                lo = tab_ld(a.src[k], b);
-                hi = tab_ld(a.src[k], b + m);
+                F9 t0, t1, t2, t3;
+                if (MODE == 1) {
+                    t0 = fr_unpack(tab_ld(a.src8[k], b));
+                    t1 = fr_unpack(tab_ld(a.src8[k], b + m));
+                    t2 = fr_unpack(tab_ld(a.src8[k], b + 2 * m));
+                    t3 = fr_unpack(tab_ld(a.src8[k], b + 3 * m));
+                } else {
+                    t0 = f9tab_ld(a.work[k], b);
+                    t1 = f9tab_ld(a.work[k], b + m);
+                    t2 = f9tab_ld(a.work[k], b + 2 * m);
+                    t3 = f9tab_ld(a.work[k], b + 3 * m);
+                }
+                lo = f9_norm_reduce(f9_add(t0, f9_mul(f9_sub(t2, t0), v)));
+                hi = f9_norm_reduce(f9_add(t1, f9_mul(f9_sub(t3, t1), v)));
+                f9tab_st(a.work[k], b, lo);
+                f9tab_st(a.work[k], b + m, hi);
             }
-            Fr d = fr_sub(hi, lo);
-            Fr cur = lo;
+            // e(x) = lo + x (hi - lo) at the points needed
+            F9 e[K + 1];
+            e[0] = lo;
+            e[1] = hi;
+            if (K >= 2) {
+                F9 dn = f9_norm(f9_sub(hi, lo));
+                e[2] = f9_add(hi, dn);
+                if (K >= 3) e[K] = f9_add(e[2], dn);
+                if (k == 0) {   // the running product needs one normal factor
+                    e[2] = f9_norm(e[2]);
+                    if (K >= 3) e[K] = f9_norm(e[K]);
+                }
+            }
 #pragma unroll
             for (int x = 0; x <= K; ++x) {
-                if (x == 1) cur = hi;
-                if (x >= 2) cur = fr_add(cur, d);
-                e[x] = (k == 0) ? cur : fr_mul(e[x], cur);
+                if (FOLD && x == 1) continue;
+                prod[x] = (k == 0) ? e[x] : f9_mul(prod[x], e[x]);
             }
         }
 #pragma unroll
-        for (int x = 0; x <= K; ++x) acc[x] = fr_add(acc[x], e[x]);
+        for (int x = 0; x <= K; ++x) {
+            if (FOLD && x == 1) continue;
+            acc[x] = f9_add(acc[x], prod[x]);
+        }
+        if (++pending == 2) {
+            pending = 0;
+#pragma unroll
+            for (int x = 0; x <= K; ++x) acc[x] = f9_norm_reduce(acc[x]);
+        }
     }
 #pragma unroll
     for (int x = 0; x <= K; ++x) {
-        Fr s = block_sum(acc[x], red);
+        Fr s = block_sum(f9_to_fr(acc[x]), red);
         if (threadIdx.x == 0) a.part[(uint64_t)blockIdx.x * (K + 1) + x] = s;
     }
 }
@@ -72,23 +111,18 @@ struct FinArgs {
     uint32_t proof_off;    // where g_t(0..npts-1) go
     int first;             // round 0: claim_0 = g(0) + g(1) is written and absorbed first
     uint32_t claim_off;
+    int derive1;           // g(1) = running claim - g(0) (the round kernel left it out)
 };
 
 // Sums the per-block partials of one round, appends g_t to the proof, absorbs it,
 // draws the round's challenge and sets the next claim g_t(v_t).
 __global__ __launch_bounds__(ZK_BLOCK) void k_sc_finalise(FinArgs a) {
-    __shared__ uint32_t red[64];
     __shared__ TsShared S;
     __shared__ Fr g[ZK_MAX_EVALS + 1];
     DevState* st = a.st;
     block_ts_load(S, st);
-    for (int x = 0; x < a.npts; ++x) {
-        Fr s = fr_zero();
-        for (int b = threadIdx.x; b < a.nblk; b += blockDim.x)
-            s = fr_add(s, a.part[(uint64_t)b * a.npts + x]);
-        s = block_sum(s, red);
-        if (threadIdx.x == 0) g[x] = s;
-    }
+    block_reduce_partials(a.part, a.nblk, a.npts, g);
+    if (a.derive1 && threadIdx.x == 0) g[1] = fr_sub(st->claim, g[0]);
     __syncthreads();
     if (a.first) {
         if (threadIdx.x == 0) g[ZK_MAX_EVALS] = fr_add(g[0], g[1]);
@@ -100,7 +134,7 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_finalise(FinArgs a) {
 }
 
 void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_t proof_off, int first,
-                        uint32_t claim_off) {
+                        uint32_t claim_off, int derive1) {
     FinArgs fa;
     fa.part = ctx->partials;
     fa.nblk = nblk;
@@ -110,6 +144,7 @@ void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_
     fa.proof_off = proof_off;
     fa.first = first;
     fa.claim_off = claim_off;
+    fa.derive1 = derive1;
     zk_prof_begin(ctx, ZKDL_PROF_FINALISE, 32.0 * npts);
     hipLaunchKernelGGL(k_sc_finalise, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, fa);
     zk_prof_end(ctx);
@@ -117,6 +152,8 @@ void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_
 
 struct FinishArgs {
     FrTab src[3];
+    F9Tab work[3];
+    int from_work;       // the length-2 tables are the lazy work tables
     int K;
     int fold;            // 1: tables have length 2 and are folded with chal; 0: length 1
     const Fr* chal;
@@ -134,11 +171,15 @@ __global__ __launch_bounds__(64) void k_sc_finish(FinishArgs a) {
     block_ts_load(S, st);
     if (threadIdx.x < (unsigned)a.K) {
         const int k = threadIdx.x;
-        Fr lo = tab_ld(a.src[k], 0);
-        if (a.fold) {
-            Fr hi = tab_ld(a.src[k], 1);
-            lo = fr_add(lo, fr_mul(*a.chal, fr_sub(hi, lo)));
+        Fr lo, hi = fr_zero();
+        if (a.from_work) {
+            lo = f9_to_fr(f9tab_ld(a.work[k], 0));
+            hi = f9_to_fr(f9tab_ld(a.work[k], 1));
+        } else {
+            lo = tab_ld(a.src[k], 0);
+            if (a.fold) hi = tab_ld(a.src[k], 1);
         }
+        if (a.fold) lo = fr_add(lo, fr_mul_ni(*a.chal, fr_sub(hi, lo)));
         f[k] = lo;
         st->scal[a.scal_base + k] = lo;
     }
@@ -146,7 +187,7 @@ __global__ __launch_bounds__(64) void k_sc_finish(FinishArgs a) {
     if (a.absorb_claim) {
         if (threadIdx.x == 0) {
             Fr c0 = f[0];
-            for (int k = 1; k < a.K; ++k) c0 = fr_mul(c0, f[k]);
+            for (int k = 1; k < a.K; ++k) c0 = fr_mul_ni(c0, f[k]);
             st->claim = c0;
             f[3] = c0;
         }
@@ -158,16 +199,23 @@ __global__ __launch_bounds__(64) void k_sc_finish(FinishArgs a) {
 }
 
 template <int K>
-static void launch_round(zkdl_ctx* ctx, bool fold, const RoundArgs& ra, unsigned grid) {
-    if (fold)
-        hipLaunchKernelGGL((k_sc_round<K, true>), dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, ra);
+static void launch_round(zkdl_ctx* ctx, int mode, const RoundArgs& ra, unsigned grid) {
+    if (mode == 0)
+        hipLaunchKernelGGL((k_sc_round<K, 0>), dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, ra);
+    else if (mode == 1)
+        hipLaunchKernelGGL((k_sc_round<K, 1>), dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, ra);
     else
-        hipLaunchKernelGGL((k_sc_round<K, false>), dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, ra);
+        hipLaunchKernelGGL((k_sc_round<K, 2>), dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, ra);
 }
 
 static const uint32_t SC_MAGIC = 0x43534B5Au;
 
-int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, const FrTab* work, int d,
+size_t zk_sumcheck_work_bytes(int K, int d) {
+    const uint64_t half = d >= 1 ? ((uint64_t)1 << (d - 1)) : 1;
+    return (size_t)K * half * 36;
+}
+
+int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, void* work_mem, int d,
                         int finals_scal_base) {
     if (K < 1 || K > 3) return ZKDL_EINVAL;
     if (ctx->n_chal + d > ZK_MAX_CHAL) return ZKDL_EINVAL;
@@ -180,33 +228,41 @@ int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, const FrTab* wor
     if (finals_off + K * 32 > (uint32_t)ZK_PROOF_CAP) return ZKDL_ESMALL;
     ctx->proof_len = finals_off + K * 32;
 
+    const uint64_t half = d >= 1 ? ((uint64_t)1 << (d - 1)) : 1;
+    F9Tab work[3];
+    for (int k = 0; k < K; ++k) {
+        work[k].p = (uint32_t*)work_mem + (size_t)k * half * 9;
+        work[k].ps = half;
+    }
     int first_chal = ctx->n_chal;
     for (int t = 0; t < d; ++t) {
         RoundArgs ra;
-        const bool fold = t > 0;
-        const FrTab* from = (t <= 1) ? src : work;
+        const int mode = t == 0 ? 0 : t == 1 ? 1 : 2;
         for (int k = 0; k < K; ++k) {
-            ra.src[k] = from[k];
-            ra.dst[k] = work[k];
+            ra.src8[k] = src[k];
+            ra.work[k] = work[k];
         }
         ra.m = (uint64_t)1 << (d - t - 1);
-        ra.chal = fold ? &ctx->dev->chal[first_chal + t - 1] : nullptr;
+        ra.chal = mode ? &ctx->dev->chal[first_chal + t - 1] : nullptr;
         ra.part = ctx->partials;
         uint64_t want = (ra.m + ZK_BLOCK - 1) / ZK_BLOCK;
         unsigned grid = (unsigned)(want > ZK_MAX_PART_BLOCKS ? ZK_MAX_PART_BLOCKS : want);
         // algorithmic bytes: per pair index and table, 2 reads (first round) or 4 reads + 2 writes
-        zk_prof_begin(ctx, fold ? ZKDL_PROF_SC_ROUND_FUSED : ZKDL_PROF_SC_ROUND_FIRST,
-                      (double)K * (fold ? 192.0 : 64.0) * (double)ra.m);
-        if (K == 1) launch_round<1>(ctx, fold, ra, grid);
-        else if (K == 2) launch_round<2>(ctx, fold, ra, grid);
-        else launch_round<3>(ctx, fold, ra, grid);
+        zk_prof_begin(ctx, mode ? ZKDL_PROF_SC_ROUND_FUSED : ZKDL_PROF_SC_ROUND_FIRST,
+                      (double)K * (mode ? 192.0 : 64.0) * (double)ra.m);
+        if (K == 1) launch_round<1>(ctx, mode, ra, grid);
+        else if (K == 2) launch_round<2>(ctx, mode, ra, grid);
+        else launch_round<3>(ctx, mode, ra, grid);
         zk_prof_end(ctx);
         zk_launch_finalise(ctx, (int)grid, npts, ctx->n_chal++, rounds_off + (uint32_t)t * npts * 32,
-                           t == 0, claim_off);
+                           t == 0, claim_off, mode != 0);
     }
     FinishArgs fi;
-    const FrTab* from = (d <= 1) ? src : work;
-    for (int k = 0; k < K; ++k) fi.src[k] = from[k];
+    for (int k = 0; k < K; ++k) {
+        fi.src[k] = src[k];
+        fi.work[k] = work[k];
+    }
+    fi.from_work = d >= 2;
     fi.K = K;
     fi.fold = d >= 1;
     fi.chal = d >= 1 ? &ctx->dev->chal[first_chal + d - 1] : nullptr;

@@ -123,16 +123,16 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_claims(ClaimsArgs a) {
     if (threadIdx.x != 0) return;
     Fr r = st->chal[a.chal_r];
     Fr rp = st->chal[a.chal_r + 1];
-    Fr r2 = fr_sqr(r);
+    Fr r2 = fr_mul_ni(r, r);
     st->weights[0] = r2;
     st->weights[1] = r;
-    st->weights[2] = fr_mul(rp, r2);
-    st->weights[3] = fr_mul(rp, r);
+    st->weights[2] = fr_mul_ni(rp, r2);
+    st->weights[3] = fr_mul_ni(rp, r);
     st->weights[4] = rp;
     Fr claim = fr_zero();
-    for (int q = 0; q < 4; ++q) claim = fr_add(claim, fr_mul(st->weights[q], c[q]));
+    for (int q = 0; q < 4; ++q) claim = fr_add(claim, fr_mul_ni(st->weights[q], c[q]));
     st->claim = claim;
-    Fr plain = fr_from_mont(claim);
+    Fr plain = fr_from_mont_ni(claim);
     uint32_t* dst = (uint32_t*)(st->proof + a.claim0_off);
     for (int l = 0; l < 8; ++l) dst[l] = plain.v[l];
 }
@@ -431,7 +431,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
         if (!present) lo = fr_zero();
         else if (a.li >= 1) {
             Fr hi = tab_ld(a.tabs.t[tid], 1);
-            lo = fr_add(lo, fr_mul(vlast, fr_sub(hi, lo)));
+            lo = fr_add(lo, fr_mul_ni(vlast, fr_sub(hi, lo)));
         }
         sc[tid] = lo;
     }
@@ -451,7 +451,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
                     val = tab_ld(col, 0);
                     if (a.li >= 2) {
                         Fr hi = tab_ld(col, 1);
-                        val = fr_add(val, fr_mul(vlast, fr_sub(hi, val)));
+                        val = fr_add(val, fr_mul_ni(vlast, fr_sub(hi, val)));
                     }
                 }
                 if (k == 0) a0 = val;
@@ -475,11 +475,11 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
     __syncthreads();
     // coefficients that stay fixed during the j-rounds
     const Fr cZ = sc[T_BZ];                          // r^2 beta_Z(v)
-    const Fr cA = fr_mul(sc[T_BA], sc[T_NS]);        // r beta_A(v) (1 - sign(v))
+    const Fr cA = fr_mul_ni(sc[T_BA], sc[T_NS]);        // r beta_A(v) (1 - sign(v))
     const Fr cGA = sc[T_BGA];
-    const Fr cGZ = fr_mul(sc[T_BGZ], sc[T_NS]);
+    const Fr cGZ = fr_mul_ni(sc[T_BGZ], sc[T_NS]);
     const Fr cB0 = sc[T_BI];                         // beta_I(v)
-    const Fr cB1 = fr_mul(st->weights[4], sc[T_BI]); // r' beta_I(v)
+    const Fr cB1 = fr_mul_ni(st->weights[4], sc[T_BI]); // r' beta_I(v)
 
     int cur = J;
     for (int t = 0; t < a.lj; ++t) {
@@ -496,12 +496,12 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
             line4(BJ[tid], BJ[tid + half], bj);
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                Fr lin0 = fr_add(fr_mul(cZ, s[x]), fr_mul(cA, sp[x]));
-                Fr lin1 = fr_add(fr_mul(cGA, s[x]), fr_mul(cGZ, sp[x]));
-                Fr q0 = fr_sub(fr_sqr(a0[x]), a0[x]);
-                Fr q1 = fr_sub(fr_sqr(a1[x]), a1[x]);
-                Fr binp = fr_mul(bj[x], fr_add(fr_mul(cB0, q0), fr_mul(cB1, q1)));
-                f[x] = fr_add(fr_add(fr_mul(lin0, a0[x]), fr_mul(lin1, a1[x])), binp);
+                Fr lin0 = fr_add(fr_mul_ni(cZ, s[x]), fr_mul_ni(cA, sp[x]));
+                Fr lin1 = fr_add(fr_mul_ni(cGA, s[x]), fr_mul_ni(cGZ, sp[x]));
+                Fr q0 = fr_sub(fr_mul_ni(a0[x], a0[x]), a0[x]);
+                Fr q1 = fr_sub(fr_mul_ni(a1[x], a1[x]), a1[x]);
+                Fr binp = fr_mul_ni(bj[x], fr_add(fr_mul_ni(cB0, q0), fr_mul_ni(cB1, q1)));
+                f[x] = fr_add(fr_add(fr_mul_ni(lin0, a0[x]), fr_mul_ni(lin1, a1[x])), binp);
             }
         }
 #pragma unroll
@@ -513,11 +513,11 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
         Fr v = block_finalise_round(TS, st, g, 4, a.rounds_off + (uint32_t)(a.li + t) * 128,
                                     a.chal_v + a.li + t);
         if (tid < half) {
-            A0[tid] = fr_add(A0[tid], fr_mul(v, fr_sub(A0[tid + half], A0[tid])));
-            A1[tid] = fr_add(A1[tid], fr_mul(v, fr_sub(A1[tid + half], A1[tid])));
-            S[tid] = fr_add(S[tid], fr_mul(v, fr_sub(S[tid + half], S[tid])));
-            SP[tid] = fr_add(SP[tid], fr_mul(v, fr_sub(SP[tid + half], SP[tid])));
-            BJ[tid] = fr_add(BJ[tid], fr_mul(v, fr_sub(BJ[tid + half], BJ[tid])));
+            A0[tid] = fr_add(A0[tid], fr_mul_ni(v, fr_sub(A0[tid + half], A0[tid])));
+            A1[tid] = fr_add(A1[tid], fr_mul_ni(v, fr_sub(A1[tid + half], A1[tid])));
+            S[tid] = fr_add(S[tid], fr_mul_ni(v, fr_sub(S[tid + half], S[tid])));
+            SP[tid] = fr_add(SP[tid], fr_mul_ni(v, fr_sub(SP[tid + half], SP[tid])));
+            BJ[tid] = fr_add(BJ[tid], fr_mul_ni(v, fr_sub(BJ[tid + half], BJ[tid])));
         }
         __syncthreads();
         cur = half;
@@ -535,9 +535,9 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
     if (tid < 3) rho[tid] = st->chal[a.chal_rho + tid];
     __syncthreads();
     if (tid == 0) {
-        Fr mc = fr_add(fr_add(fr_mul(rho[0], fin[0]), fr_mul(rho[1], fin[1])), fr_mul(rho[2], fin[2]));
+        Fr mc = fr_add(fr_add(fr_mul_ni(rho[0], fin[0]), fr_mul_ni(rho[1], fin[1])), fr_mul_ni(rho[2], fin[2]));
         st->claim = mc;
-        Fr plain = fr_from_mont(mc);
+        Fr plain = fr_from_mont_ni(mc);
         uint32_t* dst = (uint32_t*)(st->proof + a.merge_claim_off);
         for (int l = 0; l < 8; ++l) dst[l] = plain.v[l];
     }
@@ -551,7 +551,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
             Fr e, hi;
             if (tid < size) {
                 e = E[tid];
-                hi = fr_mul(e, u);
+                hi = fr_mul_ni(e, u);
             }
             __syncthreads();
             if (tid < size) {
@@ -567,10 +567,10 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
     if (tid < 64 && tid < J) bw = E[tid];
     __syncthreads();
     if (tid < 64) {
-        Fr e0 = fr_mul(rho[0], bw);
+        Fr e0 = fr_mul_ni(rho[0], bw);
         if (tid == nbits - 1) e0 = fr_add(e0, rho[2]);
         E[tid] = tid < J ? e0 : fr_zero();
-        E[64 + tid] = tid < J ? fr_mul(rho[1], bw) : fr_zero();
+        E[64 + tid] = tid < J ? fr_mul_ni(rho[1], bw) : fr_zero();
     }
     __syncthreads();
     // merge sumcheck over (k, j): k first (pairs index c with 64 + c), then the lj
@@ -598,9 +598,9 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
         if (tid < half) {
             Fr mlo = M[tid], mhi = M[tid + half], elo = E[tid], ehi = E[tid + half];
             Fr md = fr_sub(mhi, mlo), ed = fr_sub(ehi, elo);
-            f[0] = fr_mul(mlo, elo);
-            f[1] = fr_mul(mhi, ehi);
-            f[2] = fr_mul(fr_add(mhi, md), fr_add(ehi, ed));
+            f[0] = fr_mul_ni(mlo, elo);
+            f[1] = fr_mul_ni(mhi, ehi);
+            f[2] = fr_mul_ni(fr_add(mhi, md), fr_add(ehi, ed));
         }
 #pragma unroll
         for (int x = 0; x < 3; ++x) {
@@ -610,8 +610,8 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
         __syncthreads();
         Fr v = block_finalise_round(TS, st, g, 3, a.merge_rounds_off + (uint32_t)t * 96, a.chal_rho + 3 + t);
         if (tid < half) {
-            M[tid] = fr_add(M[tid], fr_mul(v, fr_sub(M[tid + half], M[tid])));
-            E[tid] = fr_add(E[tid], fr_mul(v, fr_sub(E[tid + half], E[tid])));
+            M[tid] = fr_add(M[tid], fr_mul_ni(v, fr_sub(M[tid + half], M[tid])));
+            E[tid] = fr_add(E[tid], fr_mul_ni(v, fr_sub(E[tid + half], E[tid])));
         }
         __syncthreads();
         cur = half;
@@ -788,7 +788,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
             zk_prof_end(ctx);
             nb_bin = bx * chunks;
         }
-        zk_launch_finalise(ctx, (int)(nb_lin + nb_bin), 4, c_v + t, rounds_off + (uint32_t)t * 128, 0, 0);
+        zk_launch_finalise(ctx, (int)(nb_lin + nb_bin), 4, c_v + t, rounds_off + (uint32_t)t * 128, 0, 0, 0);
         if (t == 0) {
             // bind the first challenge: bits -> field elements
             int jc = nbits;

@@ -33,9 +33,12 @@ SHA_HD uint32_t kconst(int i) {
     return K[i];
 }
 
-// one compression of a 64-byte block given as 16 big-endian words
-SHA_HD void compress(uint32_t h[8], uint32_t w[16]) {
-    uint32_t a = h[0], b = h[1], c = h[2], d = h[3], e = h[4], f = h[5], g = h[6], hh = h[7];
+// Message schedule with the round constants folded in: wk[t] = W[t] + K[t].  It does not
+// depend on the chaining value, so on the GPU it runs in other lanes than the rounds.
+SHA_HD void schedule_wk(const uint32_t w_in[16], uint32_t wk[64]) {
+    uint32_t w[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) w[i] = w_in[i];
 #pragma unroll
     for (int i = 0; i < 64; ++i) {
         if (i >= 16) {
@@ -44,16 +47,110 @@ SHA_HD void compress(uint32_t h[8], uint32_t w[16]) {
             uint32_t s1 = rotr(w2, 17) ^ rotr(w2, 19) ^ (w2 >> 10);
             w[i & 15] = w[i & 15] + s0 + w[(i + 9) & 15] + s1;
         }
+        wk[i] = w[i & 15] + kconst(i);
+    }
+}
+
+// the 64 rounds on a prepared schedule
+SHA_HD void rounds(uint32_t h[8], const uint32_t wk[64]) {
+    uint32_t a = h[0], b = h[1], c = h[2], d = h[3], e = h[4], f = h[5], g = h[6], hh = h[7];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) {
         uint32_t S1 = rotr(e, 6) ^ rotr(e, 11) ^ rotr(e, 25);
-        uint32_t ch = (e & f) ^ (~e & g);
-        uint32_t t1 = hh + S1 + ch + kconst(i) + w[i & 15];
+        uint32_t ch = (e & f) | (~e & g);              // bit select: v_bfi_b32
+        uint32_t t1 = hh + S1 + ch + wk[i];
         uint32_t S0 = rotr(a, 2) ^ rotr(a, 13) ^ rotr(a, 22);
-        uint32_t mj = (a & b) ^ (a & c) ^ (b & c);
-        uint32_t t2 = S0 + mj;
-        hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + t2;
+        uint32_t ab = a ^ b;
+        uint32_t mj = (ab & c) | (~ab & b);            // majority as a bit select
+        hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + S0 + mj;
     }
     h[0] += a; h[1] += b; h[2] += c; h[3] += d; h[4] += e; h[5] += f; h[6] += g; h[7] += hh;
 }
+
+// one compression of a 64-byte block given as 16 big-endian words
+SHA_HD void compress(uint32_t h[8], uint32_t w[16]) {
+    uint32_t wk[64];
+    schedule_wk(w, wk);
+    rounds(h, wk);
+}
+
+#if defined(__HIPCC__)
+// Compact device versions for the single-wave transcript steps.  Those steps execute
+// every instruction once per launch, from a cold instruction cache, so code bytes cost as
+// much as instructions: the bodies below are loops of 16 rounds and are not inlined.
+struct Words8 {
+    uint32_t v[8];
+};
+struct Words16 {
+    uint32_t v[16];
+};
+
+static __device__ const uint32_t K_TABLE[64] = {
+    0x428a2f98, 0x71374491, 0xb5c0fbcf, 0xe9b5dba5, 0x3956c25b, 0x59f111f1, 0x923f82a4, 0xab1c5ed5,
+    0xd807aa98, 0x12835b01, 0x243185be, 0x550c7dc3, 0x72be5d74, 0x80deb1fe, 0x9bdc06a7, 0xc19bf174,
+    0xe49b69c1, 0xefbe4786, 0x0fc19dc6, 0x240ca1cc, 0x2de92c6f, 0x4a7484aa, 0x5cb0a9dc, 0x76f988da,
+    0x983e5152, 0xa831c66d, 0xb00327c8, 0xbf597fc7, 0xc6e00bf3, 0xd5a79147, 0x06ca6351, 0x14292967,
+    0x27b70a85, 0x2e1b2138, 0x4d2c6dfc, 0x53380d13, 0x650a7354, 0x766a0abb, 0x81c2c92e, 0x92722c85,
+    0xa2bfe8a1, 0xa81a664b, 0xc24b8b70, 0xc76c51a3, 0xd192e819, 0xd6990624, 0xf40e3585, 0x106aa070,
+    0x19a4c116, 0x1e376c08, 0x2748774c, 0x34b0bcb5, 0x391c0cb3, 0x4ed8aa4a, 0x5b9cca4f, 0x682e6ff3,
+    0x748f82ee, 0x78a5636f, 0x84c87814, 0x8cc70208, 0x90befffa, 0xa4506ceb, 0xbef9a3f7, 0xc67178f2};
+
+static __device__ __noinline__ Words8 compress_ni(Words8 hin, Words16 win) {
+    uint32_t w[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) w[i] = win.v[i];
+    uint32_t a = hin.v[0], b = hin.v[1], c = hin.v[2], d = hin.v[3], e = hin.v[4], f = hin.v[5],
+             g = hin.v[6], hh = hin.v[7];
+#pragma unroll 1
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (r > 0) {
+                uint32_t w15 = w[(i + 1) & 15], w2 = w[(i + 14) & 15];
+                uint32_t s0 = rotr(w15, 7) ^ rotr(w15, 18) ^ (w15 >> 3);
+                uint32_t s1 = rotr(w2, 17) ^ rotr(w2, 19) ^ (w2 >> 10);
+                w[i] = w[i] + s0 + w[(i + 9) & 15] + s1;
+            }
+            uint32_t S1 = rotr(e, 6) ^ rotr(e, 11) ^ rotr(e, 25);
+            uint32_t ch = (e & f) | (~e & g);
+            uint32_t t1 = hh + S1 + ch + K_TABLE[16 * r + i] + w[i];
+            uint32_t S0 = rotr(a, 2) ^ rotr(a, 13) ^ rotr(a, 22);
+            uint32_t ab = a ^ b;
+            uint32_t mj = (ab & c) | (~ab & b);
+            hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + S0 + mj;
+        }
+    }
+    Words8 o;
+    o.v[0] = hin.v[0] + a; o.v[1] = hin.v[1] + b; o.v[2] = hin.v[2] + c; o.v[3] = hin.v[3] + d;
+    o.v[4] = hin.v[4] + e; o.v[5] = hin.v[5] + f; o.v[6] = hin.v[6] + g; o.v[7] = hin.v[7] + hh;
+    return o;
+}
+
+__device__ inline Words8 iv_words() {
+    Words8 h = {{0x6a09e667, 0xbb67ae85, 0x3c6ef372, 0xa54ff53a, 0x510e527f, 0x9b05688c, 0x1f83d9ab,
+                 0x5be0cd19}};
+    return h;
+}
+
+// SHA256(state || suffix [|| u32le(idx)]) through the compact compression
+__device__ inline Words8 digest_state_suffix_ni(const uint32_t st[8], uint32_t suffix, bool with_idx,
+                                                uint32_t idx) {
+    Words16 w;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w.v[i] = st[i];
+    if (with_idx) {
+        w.v[8] = (suffix << 24) | ((idx & 0xffu) << 16) | (((idx >> 8) & 0xffu) << 8) | ((idx >> 16) & 0xffu);
+        w.v[9] = ((idx >> 24) << 24) | 0x00800000u;
+    } else {
+        w.v[8] = (suffix << 24) | 0x00800000u;
+        w.v[9] = 0;
+    }
+#pragma unroll
+    for (int i = 10; i < 15; ++i) w.v[i] = 0;
+    w.v[15] = with_idx ? 37 * 8 : 33 * 8;
+    return compress_ni(iv_words(), w);
+}
+#endif
 
 // digest of msg[0..len).  The buffer must have room for the padding: its
 // capacity must be at least ((len + 9 + 63) / 64) * 64 bytes; it is overwritten.

@@ -114,14 +114,11 @@ void zk_launch_shift_rows(zkdl_ctx* ctx, FrTab src, uint64_t rows, uint64_t inne
                           FrTab out);
 
 // ---- k_sumcheck.hip ------------------------------------------------------------
-struct ScTables {
-    FrTab src[3];
-    FrTab dst[3];
-};
-// Runs all rounds of a degree-K product sumcheck on K tables of length 2^d.
-// src tables are read only; work tables (length 2^(d-1) each, if d >= 1) receive
-// the folded values.  Writes one SC block at ctx->proof_len, draws d challenges.
-int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, const FrTab* work, int d,
+// Runs all rounds of a degree-K product sumcheck on K packed tables of length 2^d.
+// The sources are read only; work_mem (zk_sumcheck_work_bytes(K, d) bytes) receives the
+// folded tables.  Writes one SC block at ctx->proof_len, draws d challenges.
+size_t zk_sumcheck_work_bytes(int K, int d);
+int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, void* work_mem, int d,
                         int finals_scal_base);
 void zk_launch_draw(zkdl_ctx* ctx, int chal_base, int count);
 
