@@ -13,11 +13,12 @@
 //    (k_zk_lin): beta*Z, beta*(1-sign)*Z', beta*G_A, beta*(1-sign)*G_A'.
 //  * Only the binarity terms need the D x (Q+R) tables (k_zk_bin*).  Their
 //    equality factor splits as beta~(u_bin,(i,j)) = beta_I(i) beta_J(j).
-//    Round 0 works on the integers directly: aux is binary, so
-//    a(x)^2 - a(x) = (x^2 - x) [bit_lo != bit_hi].  After the first challenge the
-//    tables are field elements from {0, 1, v, 1-v} and are written out once
-//    (k_zk_mat), column-major: entry (k, j, i) at plane (k*(Q+R)+j), so that
-//    threads over i read coalesced limb planes.
+//    Rounds 0 and 1 work on the integers directly: aux is binary, so in round 0
+//    a(x)^2 - a(x) = (x^2 - x) [bit_lo != bit_hi], and after the first challenge an
+//    entry is one of {0, 1, v, 1-v}, which makes round 1 a table look-up (k_zk_bin1).
+//    After the second challenge the columns are written out once (k_zk_mat2, one of
+//    16 values per entry), column-major: entry (k, j, i) at plane (k*(Q+R)+j), so
+//    that threads over i read coalesced limb planes; D/4 rows.
 //  * The j-rounds (log2 J of them) and the merge run on 64/128-entry tables in a
 //    single block (k_zk_tail) together with their transcript steps.
 #include "dev_common.cuh"
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_lin(LinArgs a) {
 struct BinArgs {
     const int64_t* z;      // round 0 / materialise only
     const int64_t* ga;
-    uint32_t* aux;         // Fr planes: entry (k, j, i) = limb planes at ((k*nbits + j)*8 + l)*ps + i
+    uint32_t* aux;         // lazy-limb planes: entry (k, j, i), limb l at ((k*nbits + j)*9 + l)*ps + i
     uint64_t ps;
     int nbits;
     int has_ga;
@@ -312,79 +313,235 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin0(BinArgs a) {
     }
 }
 
-// After the first challenge v: aux(k, v, i', j) in {0, 1, v, 1 - v} by (bit_lo, bit_hi)
-__global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat(BinArgs a) {
-    const uint64_t m = a.m;   // rows written = D / 2
-    Fr v = *a.chal;
-    Fr one = fr_one();
-    Fr omv = fr_sub(one, v);
+// ---- rounds >= 1 work on field elements; the first two challenges are bound by table look-up ----
+//
+// aux is binary, so after binding x0 = v0 an entry is one of four values, selected by the
+// two bits it interpolates: A(b_lo, b_hi) = b_lo + v0 (b_hi - b_lo), code = b_lo + 2 b_hi:
+//   code 0 -> 0, 1 -> 1 - v0, 2 -> v0, 3 -> 1.
+// Round 1 (variable x1) pairs two such entries: 16 combinations, and for each the binarity
+// summand q(x) = e(x)^2 - e(x), e(x) = A_lo + x (A_hi - A_lo), is a constant of the round.
+// So round 1 needs no table in memory at all: per (i, slice) the columns are grouped by
+// combination with bit masks, S_c = sum of beta_J over the columns of combination c, and the
+// contribution is sum_c Q_x[c] S_c: 16 products instead of 48.  After v1 the entry is one of
+// 16 values (k_zk_mat2 writes them out, D/4 rows); later rounds fold as usual.
+
+__device__ __forceinline__ F9Tab aux_col9(const BinArgs& a, int k, int j) {
+    F9Tab t;
+    t.p = a.aux + (uint64_t)(k * a.nbits + j) * 9 * a.ps;
+    t.ps = a.ps;
+    return t;
+}
+
+__device__ __forceinline__ Fr bit_pair_value(int code, const Fr& v, const Fr& one) {
+    return code == 0 ? fr_zero() : code == 3 ? one : code == 2 ? v : fr_sub(one, v);
+}
+
+// sum of beta_J (lazy limbs, LDS) over the set bits of mask; normal on return
+__device__ __forceinline__ F9 masked_sum9(const F9* sbj, uint64_t mask) {
+    F9 s = f9_zero();
+    int pending = 0;
+    while (mask) {
+        const int j = __builtin_ctzll(mask);
+        mask &= mask - 1;
+        s = f9_add(s, sbj[j]);
+        if (++pending == 4) {
+            pending = 0;
+            s = f9_norm(s);
+        }
+    }
+    return f9_norm(s);
+}
+
+// beta_I(x, i') at x = 0, 2, 3 from the pair (lo, hi) of the packed table; all normal
+__device__ __forceinline__ void beta_line(const FrTab& bI, uint64_t b, uint64_t m, F9 e[3]) {
+    F9 lo = fr_unpack(tab_ld(bI, b)), hi = fr_unpack(tab_ld(bI, b + m));
+    F9 dn = f9_norm(f9_sub(hi, lo));
+    e[0] = lo;
+    e[1] = f9_norm(f9_add(hi, dn));
+    e[2] = f9_norm(f9_add(e[1], dn));
+}
+
+// Round 1 by look-up.  m = D/4 quadruples (i'', i''+m | i''+2m, i''+3m) = (x0, x1) in
+// {(0,0), (0,1), (1,0), (1,1)}.  Writes partial sums for x = 0, 2, 3 (x = 1 comes from the claim).
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin1(BinArgs a) {
+    __shared__ uint32_t red[64];
+    __shared__ F9 sbj[64];
+    __shared__ F9 qx[2][3][16];   // [slice][x in {0,2,3}][combination]; slice 1 carries r'
+    const int tid = threadIdx.x;
+    if (tid < 64) sbj[tid] = tid < a.nbits ? fr_unpack(a.bJ[tid]) : f9_zero();
+    if (tid < 48) {
+        const int c = tid & 15, xi = tid >> 4;
+        const Fr v0 = *a.chal, one = fr_one();
+        const Fr alo = bit_pair_value(c & 3, v0, one), ahi = bit_pair_value(c >> 2, v0, one);
+        const Fr d = fr_sub(ahi, alo);
+        Fr e = alo;                                   // x = 0
+        if (xi >= 1) e = fr_add(fr_add(alo, d), d);   // x = 2
+        if (xi == 2) e = fr_add(e, d);                // x = 3
+        const Fr q = fr_sub(fr_sqr(e), e);
+        qx[0][xi][c] = fr_unpack(q);
+        qx[1][xi][c] = fr_unpack(fr_mul(*a.rp, q));
+    }
+    __syncthreads();
+    const uint64_t m = a.m;
+    const uint64_t keep = a.nbits >= 64 ? ~(uint64_t)0 : (((uint64_t)1 << a.nbits) - 1);
+    F9 tot[3];
+#pragma unroll
+    for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+        F9 acc[3];
+#pragma unroll
+        for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
+        int pending = 0;
+        for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+            const int64_t* src = k == 0 ? a.z : a.ga;
+            // (x0, x1): w00 = (0,0), w01 = (0,1), w10 = (1,0), w11 = (1,1)
+            const uint64_t w00 = (uint64_t)src[b], w01 = (uint64_t)src[b + m];
+            const uint64_t w10 = (uint64_t)src[b + 2 * m], w11 = (uint64_t)src[b + 3 * m];
+            for (int c = 0; c < 16; ++c) {
+                // lo entry (x1 = 0) interpolates bits (w00, w10); hi entry (x1 = 1) bits (w01, w11)
+                uint64_t mask = keep;
+                mask &= (c & 1) ? w00 : ~w00;
+                mask &= (c & 2) ? w10 : ~w10;
+                mask &= (c & 4) ? w01 : ~w01;
+                mask &= (c & 8) ? w11 : ~w11;
+                if (mask == 0 || c == 0 || c == 15) continue;   // q = 0 when both entries are equal bits
+                const F9 s = masked_sum9(sbj, mask);             // value < 48 r, normal
+#pragma unroll
+                for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(qx[k][x][c], s));
+                if (++pending == 2) {
+                    pending = 0;
+#pragma unroll
+                    for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
+                }
+            }
+        }
+        F9 bi[3];
+        beta_line(a.bI, b, m, bi);
+#pragma unroll
+        for (int x = 0; x < 3; ++x)
+            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_norm_reduce(acc[x]))));
+    }
+    Fr s0 = block_sum(f9_to_fr(tot[0]), red);
+    Fr s2 = block_sum(f9_to_fr(tot[1]), red);
+    Fr s3 = block_sum(f9_to_fr(tot[2]), red);
+    if (tid == 0) {
+        Fr* p = a.part + (uint64_t)blockIdx.x * 4;
+        p[0] = s0;
+        p[1] = fr_zero();
+        p[2] = s2;
+        p[3] = s3;
+    }
+}
+
+// After the second challenge: entry (k, v0, v1, i'', j) = A_lo + v1 (A_hi - A_lo), one of 16
+// values by the four bits; written as lazy limbs, D/4 rows per column.
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat2(BinArgs a) {
+    __shared__ F9 val[16];
+    if (threadIdx.x < 16) {
+        const int c = threadIdx.x;
+        const Fr v0 = a.chal[0], v1 = a.chal[1], one = fr_one();
+        const Fr alo = bit_pair_value(c & 3, v0, one), ahi = bit_pair_value(c >> 2, v0, one);
+        val[c] = fr_unpack(fr_add(alo, fr_mul(v1, fr_sub(ahi, alo))));
+    }
+    __syncthreads();
+    const uint64_t m = a.m;   // rows written = D / 4
     int j0 = blockIdx.y * a.jc, j1 = j0 + a.jc;
     if (j1 > a.nbits) j1 = a.nbits;
     for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
          b += (uint64_t)gridDim.x * blockDim.x) {
         for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
             const int64_t* src = k == 0 ? a.z : a.ga;
-            uint64_t lo = (uint64_t)src[b], hi = (uint64_t)src[b + m];
+            const uint64_t w00 = (uint64_t)src[b], w01 = (uint64_t)src[b + m];
+            const uint64_t w10 = (uint64_t)src[b + 2 * m], w11 = (uint64_t)src[b + 3 * m];
             for (int j = j0; j < j1; ++j) {
-                int bl = (lo >> j) & 1, bh = (hi >> j) & 1;
-                Fr val = bl == bh ? (bl ? one : fr_zero()) : (bh ? v : omv);
-                tab_st(aux_col(a, k, j), b, val);
+                const int c = (int)((w00 >> j) & 1) | (int)(((w10 >> j) & 1) << 1) |
+                              (int)(((w01 >> j) & 1) << 2) | (int)(((w11 >> j) & 1) << 3);
+                f9tab_st(aux_col9(a, k, j), b, val[c]);
             }
         }
     }
 }
 
-// Rounds t >= 1: per (i', j) the pair (lo, hi) of aux~(k, v.., x, i', j); the folded
-// tables are written back when FOLD.  Per thread: sum over its columns of
-// beta_J(j) (a^2 - a) at x = 0..3 for both slices, then times beta_I(x, i').
+// Rounds t >= 2 on the materialised columns (lazy limbs, same invariants as the product
+// round kernel): per (i', j, slice) the pair (lo, hi), folded with the previous challenge
+// first when FOLD; q(x) = e(x) (e(x) - 1) at x = 0, 2, 3; per thread the sum over its columns
+// of beta_J(j) q(x) (slice 1 with r' beta_J), then times beta_I(x, i').
 template <bool FOLD>
-__global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin(BinArgs a) {
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_binl(BinArgs a) {
     __shared__ uint32_t red[64];
+    __shared__ F9 sbj[2][64];
+    const int tid = threadIdx.x;
+    if (tid < 128) {
+        const int j = tid & 63, k = tid >> 6;
+        F9 x = f9_zero();
+        if (j < a.nbits) x = fr_unpack(k == 0 ? a.bJ[j] : fr_mul(*a.rp, a.bJ[j]));
+        sbj[k][j] = x;
+    }
+    __syncthreads();
     const uint64_t m = a.m;
-    Fr v = fr_zero();
-    if (FOLD) v = *a.chal;
-    Fr rp = *a.rp;
+    F9 v = f9_zero();
+    if (FOLD) v = fr_unpack(*a.chal);
+    const F9 one9 = fr_unpack(fr_one());
     int j0 = blockIdx.y * a.jc, j1 = j0 + a.jc;
     if (j1 > a.nbits) j1 = a.nbits;
-    Fr tot[4];
+    F9 tot[3];
 #pragma unroll
-    for (int x = 0; x < 4; ++x) tot[x] = fr_zero();
-    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
-         b += (uint64_t)gridDim.x * blockDim.x) {
-        Fr acc[2][4];
+    for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+        F9 acc[3];
 #pragma unroll
-        for (int k = 0; k < 2; ++k)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) acc[k][x] = fr_zero();
+        for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
+        int pending = 0;
         for (int j = j0; j < j1; ++j) {
-            Fr bj = a.bJ[j];
+            for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+                const F9Tab col = aux_col9(a, k, j);
+                F9 lo, hi;
+                if (FOLD) {
+                    const F9 t0 = f9tab_ld(col, b), t1 = f9tab_ld(col, b + m);
+                    const F9 t2 = f9tab_ld(col, b + 2 * m), t3 = f9tab_ld(col, b + 3 * m);
+                    lo = f9_norm_reduce(f9_add(t0, f9_mul(f9_sub(t2, t0), v)));
+                    hi = f9_norm_reduce(f9_add(t1, f9_mul(f9_sub(t3, t1), v)));
+                    f9tab_st(col, b, lo);
+                    f9tab_st(col, b + m, hi);
+                } else {
+                    lo = f9tab_ld(col, b);
+                    hi = f9tab_ld(col, b + m);
+                }
+                const F9 dn = f9_norm(f9_sub(hi, lo));
+                F9 e[3];
+                e[0] = lo;
+                e[1] = f9_norm(f9_add(hi, dn));
+                e[2] = f9_norm(f9_add(e[1], dn));
+                const F9 bj = sbj[k][j];
 #pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                if (k == 1 && !a.has_ga) break;
-                Fr lo, hi, e[4];
-                lin_pair<FOLD>(aux_col(a, k, j), b, m, v, lo, hi);
-                line4(lo, hi, e);
+                for (int x = 0; x < 3; ++x) {
+                    // e (e - 1): e normal, e - 1 + 4r has limbs < 2^29 + 2^30
+                    const F9 q = f9_mul(e[x], f9_sub(e[x], one9));
+                    acc[x] = f9_add(acc[x], f9_mul(bj, q));
+                }
+                if (++pending == 2) {
+                    pending = 0;
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    Fr q = fr_sub(fr_sqr(e[x]), e[x]);
-                    acc[k][x] = fr_add(acc[k][x], fr_mul(bj, q));
+                    for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
                 }
             }
         }
-        Fr lo = tab_ld(a.bI, b), hi = tab_ld(a.bI, b + m), bi[4];
-        line4(lo, hi, bi);
+        F9 bi[3];
+        beta_line(a.bI, b, m, bi);
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            Fr s = acc[0][x];
-            if (a.has_ga) s = fr_add(s, fr_mul(rp, acc[1][x]));
-            tot[x] = fr_add(tot[x], fr_mul(bi[x], s));
-        }
+        for (int x = 0; x < 3; ++x)
+            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_norm_reduce(acc[x]))));
     }
     const uint64_t blk = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        Fr s = block_sum(tot[x], red);
-        if (threadIdx.x == 0) a.part[blk * 4 + x] = s;
+    Fr s0 = block_sum(f9_to_fr(tot[0]), red);
+    Fr s2 = block_sum(f9_to_fr(tot[1]), red);
+    Fr s3 = block_sum(f9_to_fr(tot[2]), red);
+    if (tid == 0) {
+        Fr* p = a.part + blk * 4;
+        p[0] = s0;
+        p[1] = fr_zero();
+        p[2] = s2;
+        p[3] = s3;
     }
 }
 
@@ -446,11 +603,17 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
                 if (a.li == 0) {
                     const int64_t* src = k == 0 ? a.bin.z : a.bin.ga;
                     val = (((uint64_t)src[0] >> j) & 1) ? one : fr_zero();
+                } else if (a.li == 1) {
+                    // one challenge: the entry interpolates the bits of the two integers
+                    const int64_t* src = k == 0 ? a.bin.z : a.bin.ga;
+                    const int code = (int)(((uint64_t)src[0] >> j) & 1) | (int)((((uint64_t)src[1] >> j) & 1) << 1);
+                    val = bit_pair_value(code, vlast, one);
                 } else {
-                    FrTab col = aux_col(a.bin, k, j);
-                    val = tab_ld(col, 0);
-                    if (a.li >= 2) {
-                        Fr hi = tab_ld(col, 1);
+                    // the columns were written after the second challenge; later rounds folded them
+                    F9Tab col = aux_col9(a.bin, k, j);
+                    val = f9_to_fr(f9tab_ld(col, 0));
+                    if (a.li >= 3) {
+                        Fr hi = f9_to_fr(f9tab_ld(col, 1));
                         val = fr_add(val, fr_mul_ni(vlast, fr_sub(hi, val)));
                     }
                 }
@@ -678,10 +841,10 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     DevState* st = ctx->dev;
     zk_launch_draw(ctx, c0, 5 * li + lj);
 
-    // memory: 10 D-sized tables, beta_J, aux planes (2 * nbits columns of D/2 rows)
-    const uint64_t rows = D >= 2 ? D / 2 : 1;
+    // memory: 10 D-sized tables, beta_J, aux columns (2 * nbits columns of D/4 rows, 36 B entries)
+    const uint64_t rows = D >= 4 ? D / 4 : 1;
     const uint64_t aux_elems = (uint64_t)(has_ga ? 2 : 1) * nbits * rows;
-    void* mem = zk_alloc(ctx, ((uint64_t)LIN_TABLES * D + 64 + (li >= 1 ? aux_elems : 0)) * 32);
+    void* mem = zk_alloc(ctx, ((uint64_t)LIN_TABLES * D + 64) * 32 + (li >= 2 ? aux_elems * 36 : 0));
     if (!mem) return ZKDL_ENOMEM;
     uint32_t* base = (uint32_t*)mem;
     ZkTabs tabs;
@@ -699,13 +862,9 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     if (rc == ZKDL_OK && has_ga) rc = zk_build_beta(ctx, st->chal + c_ugz, li, tabs.t[T_BGZ]);
     if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ubin, li, tabs.t[T_BI]);
     // beta_J as an array of structures: one plane of J elements read through FrTab, then copied
-    FrTab bj_soa = make_tab(aux, J);   // aux is not in use yet (or absent: then scratch below)
-    void* bj_tmp = nullptr;
-    if (li < 1) {
-        bj_tmp = zk_alloc(ctx, 64 * 32);
-        if (!bj_tmp) rc = ZKDL_ENOMEM;
-        bj_soa = make_tab(bj_tmp, J);
-    }
+    void* bj_tmp = zk_alloc(ctx, 64 * 32);
+    if (!bj_tmp) rc = ZKDL_ENOMEM;
+    FrTab bj_soa = make_tab(bj_tmp, J);
     if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ubin + li, lj, bj_soa);
     if (rc != ZKDL_OK) {
         zk_free(ctx, bj_tmp);
@@ -773,6 +932,13 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
             zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, (has_ga ? 32.0 : 16.0) * (double)m + 64.0 * (double)m);
             hipLaunchKernelGGL(k_zk_bin0, dim3(nb_bin), dim3(ZK_BLOCK), 0, ctx->stream, ba);
             zk_prof_end(ctx);
+        } else if (t == 1) {
+            // second round: look-up on the integers, nothing in memory yet
+            nb_bin = blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
+            ba.chal = &st->chal[c_v];
+            zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, (has_ga ? 64.0 : 32.0) * (double)m + 64.0 * (double)m);
+            hipLaunchKernelGGL(k_zk_bin1, dim3(nb_bin), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            zk_prof_end(ctx);
         } else {
             // few rows: split the columns over more threads
             int jc = nbits;
@@ -780,23 +946,25 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
             unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
             unsigned bx = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / chunks);
             ba.jc = jc;
-            ba.chal = t >= 2 ? &st->chal[c_v + t - 1] : nullptr;
+            ba.chal = t >= 3 ? &st->chal[c_v + t - 1] : nullptr;
             zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN,
-                          (has_ga ? 2.0 : 1.0) * nbits * (t >= 2 ? 192.0 : 64.0) * (double)m + 64.0 * (double)m);
-            if (t >= 2) hipLaunchKernelGGL(k_zk_bin<true>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
-            else hipLaunchKernelGGL(k_zk_bin<false>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+                          (has_ga ? 2.0 : 1.0) * nbits * (t >= 3 ? 192.0 : 64.0) * (double)m + 64.0 * (double)m);
+            if (t >= 3) hipLaunchKernelGGL(k_zk_binl<true>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            else hipLaunchKernelGGL(k_zk_binl<false>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
             zk_prof_end(ctx);
             nb_bin = bx * chunks;
         }
-        zk_launch_finalise(ctx, (int)(nb_lin + nb_bin), 4, c_v + t, rounds_off + (uint32_t)t * 128, 0, 0, 0);
-        if (t == 0) {
-            // bind the first challenge: bits -> field elements
+        // g(1) is taken from the running claim: the binarity kernels leave it out
+        zk_launch_finalise(ctx, (int)(nb_lin + nb_bin), 4, c_v + t, rounds_off + (uint32_t)t * 128, 0, 0, 1);
+        if (t == 1) {
+            // bind the first two challenges: bits -> field elements, D/4 rows per column
             int jc = nbits;
             while ((uint64_t)((nbits + jc - 1) / jc) * m < 32768 && jc > 1) jc = (jc + 1) / 2;
             unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
             ba.jc = jc;
             ba.chal = &st->chal[c_v];
-            hipLaunchKernelGGL(k_zk_mat, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            ba.m = m;
+            hipLaunchKernelGGL(k_zk_mat2, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
         }
     }
     TailArgs ta;
