@@ -27,68 +27,74 @@ struct RoundArgs {
 //   evaluation points: e(2) = hi + dn, e(3) = e(2) + dn with dn = norm(hi - lo + 4r):
 //   limbs < 2^30.6, and every product has one normal factor;
 //   sums are renormalised and reduced after every second addition.
+// one pair index: fold (fused modes), evaluate, add the products to acc
 template <int K, int MODE>
-__global__ __launch_bounds__(ZK_BLOCK) void k_sc_round(RoundArgs a) {
-    __shared__ uint32_t red[64];
+__device__ __forceinline__ void sc_pair(const RoundArgs& a, uint64_t b, uint64_t m, const F9& v, F9 acc[K + 1]) {
     constexpr bool FOLD = MODE != 0;
-    F9 acc[K + 1];
+    F9 prod[K + 1];
 #pragma unroll
-    for (int x = 0; x <= K; ++x) acc[x] = f9_zero();
-    F9 v = f9_zero();
-    if (FOLD) v = fr_unpack(*a.chal);
-    const uint64_t m = a.m;
-    int pending = 0;
-    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
-         b += (uint64_t)gridDim.x * blockDim.x) {
-        F9 prod[K + 1];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            F9 lo, hi;
-            if (MODE == 0) {
-                lo = fr_unpack(tab_ld(a.src8[k], b));
-                hi = fr_unpack(tab_ld(a.src8[k], b + m));
+    for (int k = 0; k < K; ++k) {
+        F9 lo, hi;
+        if (MODE == 0) {
+            lo = fr_unpack(tab_ld(a.src8[k], b));
+            hi = fr_unpack(tab_ld(a.src8[k], b + m));
+        } else {
+            F9 t0, t1, t2, t3;
+            if (MODE == 1) {
+                t0 = fr_unpack(tab_ld(a.src8[k], b));
+                t1 = fr_unpack(tab_ld(a.src8[k], b + m));
+                t2 = fr_unpack(tab_ld(a.src8[k], b + 2 * m));
+                t3 = fr_unpack(tab_ld(a.src8[k], b + 3 * m));
             } else {
-                F9 t0, t1, t2, t3;
-                if (MODE == 1) {
-                    t0 = fr_unpack(tab_ld(a.src8[k], b));
-                    t1 = fr_unpack(tab_ld(a.src8[k], b + m));
-                    t2 = fr_unpack(tab_ld(a.src8[k], b + 2 * m));
-                    t3 = fr_unpack(tab_ld(a.src8[k], b + 3 * m));
-                } else {
-                    t0 = f9tab_ld(a.work[k], b);
-                    t1 = f9tab_ld(a.work[k], b + m);
-                    t2 = f9tab_ld(a.work[k], b + 2 * m);
-                    t3 = f9tab_ld(a.work[k], b + 3 * m);
-                }
-                lo = f9_norm_reduce(f9_add(t0, f9_mul(f9_sub(t2, t0), v)));
-                hi = f9_norm_reduce(f9_add(t1, f9_mul(f9_sub(t3, t1), v)));
-                f9tab_st(a.work[k], b, lo);
-                f9tab_st(a.work[k], b + m, hi);
+                t0 = f9tab_ld(a.work[k], b);
+                t1 = f9tab_ld(a.work[k], b + m);
+                t2 = f9tab_ld(a.work[k], b + 2 * m);
+                t3 = f9tab_ld(a.work[k], b + 3 * m);
             }
-            // e(x) = lo + x (hi - lo) at the points needed
-            F9 e[K + 1];
-            e[0] = lo;
-            e[1] = hi;
-            if (K >= 2) {
-                F9 dn = f9_norm(f9_sub(hi, lo));
-                e[2] = f9_add(hi, dn);
-                if (K >= 3) e[K] = f9_add(e[2], dn);
-                if (k == 0) {   // the running product needs one normal factor
-                    e[2] = f9_norm(e[2]);
-                    if (K >= 3) e[K] = f9_norm(e[K]);
-                }
-            }
-#pragma unroll
-            for (int x = 0; x <= K; ++x) {
-                if (FOLD && x == 1) continue;
-                prod[x] = (k == 0) ? e[x] : f9_mul(prod[x], e[x]);
+            lo = f9_norm_reduce(f9_add(t0, f9_mul(f9_sub(t2, t0), v)));
+            hi = f9_norm_reduce(f9_add(t1, f9_mul(f9_sub(t3, t1), v)));
+            f9tab_st(a.work[k], b, lo);
+            f9tab_st(a.work[k], b + m, hi);
+        }
+        // e(x) = lo + x (hi - lo) at the points needed
+        F9 e[K + 1];
+        e[0] = lo;
+        e[1] = hi;
+        if (K >= 2) {
+            F9 dn = f9_norm(f9_sub(hi, lo));
+            e[2] = f9_add(hi, dn);
+            if (K >= 3) e[K] = f9_add(e[2], dn);
+            if (k == 0) {   // the running product needs one normal factor
+                e[2] = f9_norm(e[2]);
+                if (K >= 3) e[K] = f9_norm(e[K]);
             }
         }
 #pragma unroll
         for (int x = 0; x <= K; ++x) {
             if (FOLD && x == 1) continue;
-            acc[x] = f9_add(acc[x], prod[x]);
+            prod[x] = (k == 0) ? e[x] : f9_mul(prod[x], e[x]);
         }
+    }
+#pragma unroll
+    for (int x = 0; x <= K; ++x) {
+        if (FOLD && x == 1) continue;
+        acc[x] = f9_add(acc[x], prod[x]);
+    }
+}
+
+template <int K, int MODE>
+__global__ __launch_bounds__(ZK_BLOCK) void k_sc_round(RoundArgs a) {
+    __shared__ uint32_t red[64];
+    F9 acc[K + 1];
+#pragma unroll
+    for (int x = 0; x <= K; ++x) acc[x] = f9_zero();
+    F9 v = f9_zero();
+    if (MODE != 0) v = fr_unpack(*a.chal);
+    const uint64_t m = a.m;
+    int pending = 0;
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
+         b += (uint64_t)gridDim.x * blockDim.x) {
+        sc_pair<K, MODE>(a, b, m, v, acc);
         if (++pending == 2) {
             pending = 0;
 #pragma unroll
@@ -198,6 +204,75 @@ __global__ __launch_bounds__(64) void k_sc_finish(FinishArgs a) {
     block_ts_store(S, st);
 }
 
+struct ScTailArgs {
+    RoundArgs ra;          // work tables; ra.m = pairs of the first round handled here
+    int rounds;            // rounds handled here (the last ones of the sumcheck)
+    int first_chal;        // challenge index of the round before the first one handled here
+    DevState* st;
+    uint32_t rounds_off;   // proof offset of g of the first round handled here
+    uint32_t finals_off;
+    int scal_base;
+};
+
+// The last rounds of a product sumcheck in one block: once a round has at most a few
+// pairs per thread, a kernel launch per round costs more than the round.  Same arithmetic
+// as k_sc_round<K, 2>, round after round with barriers in between, then the final fold.
+template <int K>
+__global__ __launch_bounds__(ZK_BLOCK) void k_sc_tail(ScTailArgs a) {
+    __shared__ uint32_t red[64];
+    __shared__ TsShared S;
+    __shared__ Fr g[ZK_MAX_EVALS + 1];
+    DevState* st = a.st;
+    block_ts_load(S, st);
+    uint64_t m = a.ra.m;
+    F9 v = fr_unpack(st->chal[a.first_chal]);
+    for (int t = 0; t < a.rounds; ++t) {
+        F9 acc[K + 1];
+#pragma unroll
+        for (int x = 0; x <= K; ++x) acc[x] = f9_zero();
+        int pending = 0;
+        for (uint64_t b = threadIdx.x; b < m; b += blockDim.x) {
+            sc_pair<K, 2>(a.ra, b, m, v, acc);
+            if (++pending == 2) {
+                pending = 0;
+#pragma unroll
+                for (int x = 0; x <= K; ++x) acc[x] = f9_norm_reduce(acc[x]);
+            }
+        }
+#pragma unroll
+        for (int x = 0; x <= K; ++x) {
+            if (x == 1) continue;
+            Fr s = block_sum(f9_to_fr(acc[x]), red);
+            if (threadIdx.x == 0) g[x] = s;
+        }
+        if (threadIdx.x == 0) g[1] = fr_sub(st->claim, g[0]);
+        __syncthreads();
+        Fr vr = block_finalise_round(S, st, g, K + 1, a.rounds_off + (uint32_t)t * (K + 1) * 32,
+                                     a.first_chal + 1 + t);
+        __syncthreads();   // the claim and the folded tables are read by other threads next round
+        v = fr_unpack(vr);
+        m >>= 1;
+    }
+    // final fold of the length-2 tables, finals into the proof and the transcript
+    __shared__ Fr f[4];
+    if (threadIdx.x < K) {
+        const int k = threadIdx.x;
+        Fr lo = f9_to_fr(f9tab_ld(a.ra.work[k], 0));
+        Fr hi = f9_to_fr(f9tab_ld(a.ra.work[k], 1));
+        lo = fr_add(lo, fr_mul_ni(fr_pack(f9_cond_sub(f9_norm_reduce(v))), fr_sub(hi, lo)));
+        f[k] = lo;
+        st->scal[a.scal_base + k] = lo;
+    }
+    __syncthreads();
+    block_absorb_frs(S, 'f', f, K, (uint32_t*)(st->proof + a.finals_off));
+    block_ts_store(S, st);
+}
+
+template <int K>
+static void launch_tail(zkdl_ctx* ctx, const ScTailArgs& ta) {
+    hipLaunchKernelGGL((k_sc_tail<K>), dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ta);
+}
+
 template <int K>
 static void launch_round(zkdl_ctx* ctx, int mode, const RoundArgs& ra, unsigned grid) {
     if (mode == 0)
@@ -235,7 +310,10 @@ int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, void* work_mem, 
         work[k].ps = half;
     }
     int first_chal = ctx->n_chal;
-    for (int t = 0; t < d; ++t) {
+    // the last rounds (at most SC_TAIL_LOG of them, never the first two) run in one block
+    constexpr int SC_TAIL_LOG = 10;
+    const int t_tail = d >= 3 ? (d - SC_TAIL_LOG > 2 ? d - SC_TAIL_LOG : 2) : d;
+    for (int t = 0; t < t_tail; ++t) {
         RoundArgs ra;
         const int mode = t == 0 ? 0 : t == 1 ? 1 : 2;
         for (int k = 0; k < K; ++k) {
@@ -256,6 +334,27 @@ int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, void* work_mem, 
         zk_prof_end(ctx);
         zk_launch_finalise(ctx, (int)grid, npts, ctx->n_chal++, rounds_off + (uint32_t)t * npts * 32,
                            t == 0, claim_off, mode != 0);
+    }
+    if (t_tail < d) {
+        ScTailArgs ta;
+        for (int k = 0; k < K; ++k) {
+            ta.ra.src8[k] = src[k];
+            ta.ra.work[k] = work[k];
+        }
+        ta.ra.m = (uint64_t)1 << (d - t_tail - 1);
+        ta.ra.chal = nullptr;
+        ta.ra.part = nullptr;
+        ta.rounds = d - t_tail;
+        ta.first_chal = first_chal + t_tail - 1;
+        ta.st = ctx->dev;
+        ta.rounds_off = rounds_off + (uint32_t)t_tail * npts * 32;
+        ta.finals_off = finals_off;
+        ta.scal_base = finals_scal_base;
+        ctx->n_chal += d - t_tail;
+        if (K == 1) launch_tail<1>(ctx, ta);
+        else if (K == 2) launch_tail<2>(ctx, ta);
+        else launch_tail<3>(ctx, ta);
+        return ZKDL_OK;
     }
     FinishArgs fi;
     for (int k = 0; k < K; ++k) {

@@ -12,7 +12,7 @@
 
 constexpr int ZK_MAX_CHAL = 1024;          // challenges one call may draw
 constexpr int ZK_PROOF_CAP = 1 << 17;      // proof bytes one call may write
-constexpr int ZK_MAX_PART_BLOCKS = 2048;   // partial-sum slots of a round kernel
+constexpr int ZK_MAX_PART_BLOCKS = 1024;   // partial-sum slots of a round kernel
 constexpr int ZK_MAX_EVALS = 4;            // evaluations per round polynomial (degree <= 3)
 constexpr int ZK_BLOCK = 256;
 
