@@ -29,8 +29,13 @@ constexpr int LIN_TABLES = 10;
 // order of the D-sized tables
 enum { T_BZ = 0, T_Z, T_BA, T_NS, T_ZP, T_BGA, T_GA, T_BGZ, T_GAP, T_BI };
 
+// The D-sized tables live as lazy 29-bit limbs (nine planes): they are folded every round.
 struct ZkTabs {
-    FrTab t[LIN_TABLES];
+    F9Tab t[LIN_TABLES];
+};
+// the five equality tables as built (packed): beta_Z, beta_A, beta_GA, beta_GZ, beta_I
+struct ZkBeta8 {
+    FrTab t[5];
 };
 
 __device__ __forceinline__ int64_t rescale_half_up(int64_t x, int r_bits) {
@@ -52,7 +57,8 @@ struct PrepArgs {
     const int64_t* ga;   // nullptr: G_A = 0
     uint64_t D;
     int nbits, r_bits;
-    ZkTabs tabs;         // beta tables are read, value tables written
+    ZkBeta8 beta;        // packed equality tables, read
+    ZkTabs tabs;         // value tables, written
     Fr* part;            // per block: 4 partial dot products
     DevState* st;
 };
@@ -70,20 +76,20 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_prepare(PrepArgs a) {
         bool neg = (z >> (a.nbits - 1)) & 1;            // aux(0, i, Q+R-1)
         int64_t zp = rescale_half_up(z, a.r_bits);
         Fr fz = fr_from_i64(z), fzp = fr_from_i64(zp);
-        tab_st(a.tabs.t[T_Z], i, fz);
-        tab_st(a.tabs.t[T_ZP], i, fzp);
-        tab_st(a.tabs.t[T_NS], i, neg ? fr_zero() : fr_one());
-        acc[0] = fr_add(acc[0], fr_mul(tab_ld(a.tabs.t[T_BZ], i), fz));
-        if (!neg) acc[1] = fr_add(acc[1], fr_mul(tab_ld(a.tabs.t[T_BA], i), fzp));
+        f9tab_st(a.tabs.t[T_Z], i, fr_unpack(fz));
+        f9tab_st(a.tabs.t[T_ZP], i, fr_unpack(fzp));
+        f9tab_st(a.tabs.t[T_NS], i, fr_unpack(neg ? fr_zero() : fr_one()));
+        acc[0] = fr_add(acc[0], fr_mul(tab_ld(a.beta.t[0], i), fz));
+        if (!neg) acc[1] = fr_add(acc[1], fr_mul(tab_ld(a.beta.t[1], i), fzp));
         if (a.ga) {
             int64_t g = a.ga[i];
             bad |= !in_range(g, a.nbits);
             int64_t gp = rescale_half_up(g, a.r_bits);
             Fr fg = fr_from_i64(g), fgp = fr_from_i64(gp);
-            tab_st(a.tabs.t[T_GA], i, fg);
-            tab_st(a.tabs.t[T_GAP], i, fgp);
-            acc[2] = fr_add(acc[2], fr_mul(tab_ld(a.tabs.t[T_BGA], i), fg));
-            if (!neg) acc[3] = fr_add(acc[3], fr_mul(tab_ld(a.tabs.t[T_BGZ], i), fgp));
+            f9tab_st(a.tabs.t[T_GA], i, fr_unpack(fg));
+            f9tab_st(a.tabs.t[T_GAP], i, fr_unpack(fgp));
+            acc[2] = fr_add(acc[2], fr_mul(tab_ld(a.beta.t[2], i), fg));
+            if (!neg) acc[3] = fr_add(acc[3], fr_mul(tab_ld(a.beta.t[3], i), fgp));
         }
     }
     if (bad) atomicOr(&a.st->err, 1u);
@@ -138,17 +144,20 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_claims(ClaimsArgs a) {
     for (int l = 0; l < 8; ++l) dst[l] = plain.v[l];
 }
 
-// the equation weights go into the four beta tables: beta_Z *= r^2, beta_A *= r, ...
-__global__ __launch_bounds__(ZK_BLOCK) void k_zk_scale(ZkTabs tabs, uint64_t D, const Fr* weights, int has_ga) {
+// the equation weights go into the four equality tables (beta_Z *= r^2, beta_A *= r, ...);
+// all five are rewritten as lazy limbs for the rounds
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_scale(ZkBeta8 beta, ZkTabs tabs, uint64_t D, const Fr* weights,
+                                                       int has_ga) {
     Fr w0 = weights[0], w1 = weights[1], w2 = weights[2], w3 = weights[3];
     for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < D;
          i += (uint64_t)gridDim.x * blockDim.x) {
-        tab_st(tabs.t[T_BZ], i, fr_mul(tab_ld(tabs.t[T_BZ], i), w0));
-        tab_st(tabs.t[T_BA], i, fr_mul(tab_ld(tabs.t[T_BA], i), w1));
+        f9tab_st(tabs.t[T_BZ], i, fr_unpack(fr_mul(tab_ld(beta.t[0], i), w0)));
+        f9tab_st(tabs.t[T_BA], i, fr_unpack(fr_mul(tab_ld(beta.t[1], i), w1)));
         if (has_ga) {
-            tab_st(tabs.t[T_BGA], i, fr_mul(tab_ld(tabs.t[T_BGA], i), w2));
-            tab_st(tabs.t[T_BGZ], i, fr_mul(tab_ld(tabs.t[T_BGZ], i), w3));
+            f9tab_st(tabs.t[T_BGA], i, fr_unpack(fr_mul(tab_ld(beta.t[2], i), w2)));
+            f9tab_st(tabs.t[T_BGZ], i, fr_unpack(fr_mul(tab_ld(beta.t[3], i), w3)));
         }
+        f9tab_st(tabs.t[T_BI], i, fr_unpack(tab_ld(beta.t[4], i)));
     }
 }
 
@@ -163,80 +172,93 @@ struct LinArgs {
     int has_ga;
 };
 
+// pair (lo, hi) of a lazy table, folded with the previous challenge first when FOLD; both
+// normal with value < 2.41 r (the invariants of the product round kernel apply)
 template <bool FOLD>
-__device__ __forceinline__ void lin_pair(const FrTab& t, uint64_t b, uint64_t m, const Fr& v, Fr& lo, Fr& hi) {
+__device__ __forceinline__ void lin_pair(const F9Tab& t, uint64_t b, uint64_t m, const F9& v, F9& lo, F9& hi) {
     if (FOLD) {
-        Fr t0 = tab_ld(t, b), t1 = tab_ld(t, b + m), t2 = tab_ld(t, b + 2 * m), t3 = tab_ld(t, b + 3 * m);
-        lo = fr_add(t0, fr_mul(v, fr_sub(t2, t0)));
-        hi = fr_add(t1, fr_mul(v, fr_sub(t3, t1)));
-        tab_st(t, b, lo);
-        tab_st(t, b + m, hi);
+        const F9 t0 = f9tab_ld(t, b), t1 = f9tab_ld(t, b + m), t2 = f9tab_ld(t, b + 2 * m), t3 = f9tab_ld(t, b + 3 * m);
+        lo = f9_norm_reduce(f9_add(t0, f9_mul(f9_sub(t2, t0), v)));
+        hi = f9_norm_reduce(f9_add(t1, f9_mul(f9_sub(t3, t1), v)));
+        f9tab_st(t, b, lo);
+        f9tab_st(t, b + m, hi);
     } else {
-        lo = tab_ld(t, b);
-        hi = tab_ld(t, b + m);
+        lo = f9tab_ld(t, b);
+        hi = f9tab_ld(t, b + m);
     }
 }
 
-// values of lo + x (hi - lo) at x = 0..3
-__device__ __forceinline__ void line4(const Fr& lo, const Fr& hi, Fr e[4]) {
-    Fr d = fr_sub(hi, lo);
+// lo + x (hi - lo) at x = 0, 2, 3; NORMAL: all three normal, else limbs below 2^30.6
+template <bool NORMAL>
+__device__ __forceinline__ void line3(const F9& lo, const F9& hi, F9 e[3]) {
+    const F9 dn = f9_norm(f9_sub(hi, lo));
     e[0] = lo;
-    e[1] = hi;
-    e[2] = fr_add(hi, d);
-    e[3] = fr_add(e[2], d);
+    e[1] = f9_add(hi, dn);
+    e[2] = f9_add(e[1], dn);
+    if (NORMAL) {
+        e[1] = f9_norm(e[1]);
+        e[2] = f9_norm(e[2]);
+    }
 }
 
+// Linear equations of one i-round: sum over i' of
+//   (r^2 beta_Z) Z + (r beta_A)(1 - sign) Z' + (r'r^2 beta_GA) G_A + (r'r beta_GZ)(1 - sign) G_A'
+// at x = 0, 2, 3 (x = 1 comes from the claim); beta_I is folded along for the binarity kernels.
 template <bool FOLD>
 __global__ __launch_bounds__(ZK_BLOCK) void k_zk_lin(LinArgs a) {
     __shared__ uint32_t red[64];
-    Fr acc[4];
+    F9 acc[3];
 #pragma unroll
-    for (int x = 0; x < 4; ++x) acc[x] = fr_zero();
-    Fr v = fr_zero();
-    if (FOLD) v = *a.chal;
+    for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
+    F9 v = f9_zero();
+    if (FOLD) v = fr_unpack(*a.chal);
     const uint64_t m = a.m;
     for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
          b += (uint64_t)gridDim.x * blockDim.x) {
-        Fr lo, hi, ns[4], p[4], q[4];
+        F9 lo, hi, ns[3], p[3], q[3];
         lin_pair<FOLD>(a.tabs.t[T_NS], b, m, v, lo, hi);
-        line4(lo, hi, ns);
-        // the equality table of the binarity terms is only carried along here
+        line3<false>(lo, hi, ns);
         lin_pair<FOLD>(a.tabs.t[T_BI], b, m, v, lo, hi);
-        // r^2 beta_Z * Z
         lin_pair<FOLD>(a.tabs.t[T_BZ], b, m, v, lo, hi);
-        line4(lo, hi, p);
+        line3<true>(lo, hi, p);
         lin_pair<FOLD>(a.tabs.t[T_Z], b, m, v, lo, hi);
-        line4(lo, hi, q);
+        line3<false>(lo, hi, q);
 #pragma unroll
-        for (int x = 0; x < 4; ++x) acc[x] = fr_add(acc[x], fr_mul(p[x], q[x]));
-        // r beta_A * (1 - sign) * Z'
+        for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
         lin_pair<FOLD>(a.tabs.t[T_BA], b, m, v, lo, hi);
-        line4(lo, hi, p);
+        line3<true>(lo, hi, p);
         lin_pair<FOLD>(a.tabs.t[T_ZP], b, m, v, lo, hi);
-        line4(lo, hi, q);
+        line3<false>(lo, hi, q);
 #pragma unroll
-        for (int x = 0; x < 4; ++x) acc[x] = fr_add(acc[x], fr_mul(fr_mul(p[x], ns[x]), q[x]));
+        for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(f9_mul(p[x], ns[x]), q[x]));
+#pragma unroll
+        for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
         if (a.has_ga) {
-            // r' r^2 beta_GA * G_A
             lin_pair<FOLD>(a.tabs.t[T_BGA], b, m, v, lo, hi);
-            line4(lo, hi, p);
+            line3<true>(lo, hi, p);
             lin_pair<FOLD>(a.tabs.t[T_GA], b, m, v, lo, hi);
-            line4(lo, hi, q);
+            line3<false>(lo, hi, q);
 #pragma unroll
-            for (int x = 0; x < 4; ++x) acc[x] = fr_add(acc[x], fr_mul(p[x], q[x]));
-            // r' r beta_GZ * (1 - sign) * G_A'
+            for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
             lin_pair<FOLD>(a.tabs.t[T_BGZ], b, m, v, lo, hi);
-            line4(lo, hi, p);
+            line3<true>(lo, hi, p);
             lin_pair<FOLD>(a.tabs.t[T_GAP], b, m, v, lo, hi);
-            line4(lo, hi, q);
+            line3<false>(lo, hi, q);
 #pragma unroll
-            for (int x = 0; x < 4; ++x) acc[x] = fr_add(acc[x], fr_mul(fr_mul(p[x], ns[x]), q[x]));
+            for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(f9_mul(p[x], ns[x]), q[x]));
+#pragma unroll
+            for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
         }
     }
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        Fr s = block_sum(acc[x], red);
-        if (threadIdx.x == 0) a.part[(uint64_t)blockIdx.x * 4 + x] = s;
+    Fr s0 = block_sum(f9_to_fr(acc[0]), red);
+    Fr s2 = block_sum(f9_to_fr(acc[1]), red);
+    Fr s3 = block_sum(f9_to_fr(acc[2]), red);
+    if (threadIdx.x == 0) {
+        Fr* pp = a.part + (uint64_t)blockIdx.x * 4;
+        pp[0] = s0;
+        pp[1] = fr_zero();
+        pp[2] = s2;
+        pp[3] = s3;
     }
 }
 
@@ -253,7 +275,7 @@ struct BinArgs {
     uint64_t m;            // pairs this round
     int jc;                // columns per thread
     const Fr* chal;
-    FrTab bI;
+    F9Tab bI;              // beta_I, lazy limbs (folded by the linear kernel of the same round)
     const Fr* bJ;          // J entries
     const Fr* rp;          // r'
     Fr* part;              // partials of this kernel
@@ -294,7 +316,8 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin0(BinArgs a) {
             uint64_t dg = ((uint64_t)a.ga[b] ^ (uint64_t)a.ga[b + m]) & keep;
             c = fr_add(c, fr_mul(rp, masked_sum(sbj, dg, a.nbits)));
         }
-        Fr lo = tab_ld(a.bI, b), hi = tab_ld(a.bI, b + m);
+        // round 0: the table is as built, fully reduced
+        Fr lo = fr_pack(f9tab_ld(a.bI, b)), hi = fr_pack(f9tab_ld(a.bI, b + m));
         Fr d = fr_sub(hi, lo);
         Fr b2 = fr_add(hi, d), b3 = fr_add(b2, d);
         Fr c2 = fr_dbl(c);                       // (x^2 - x) = 2 at x = 2
@@ -353,8 +376,8 @@ __device__ __forceinline__ F9 masked_sum9(const F9* sbj, uint64_t mask) {
 }
 
 // beta_I(x, i') at x = 0, 2, 3 from the pair (lo, hi) of the packed table; all normal
-__device__ __forceinline__ void beta_line(const FrTab& bI, uint64_t b, uint64_t m, F9 e[3]) {
-    F9 lo = fr_unpack(tab_ld(bI, b)), hi = fr_unpack(tab_ld(bI, b + m));
+__device__ __forceinline__ void beta_line(const F9Tab& bI, uint64_t b, uint64_t m, F9 e[3]) {
+    F9 lo = f9tab_ld(bI, b), hi = f9tab_ld(bI, b + m);
     F9 dn = f9_norm(f9_sub(hi, lo));
     e[0] = lo;
     e[1] = f9_norm(f9_add(hi, dn));
@@ -560,20 +583,39 @@ struct TailArgs {
     uint32_t merge_claim_off, merge_rounds_off, merge_finals_off;
 };
 
-constexpr int TAIL_THREADS = 128;
+constexpr int TAIL_THREADS = 256;
 
-__device__ __forceinline__ Fr tail_block_sum(Fr x, uint32_t* red) { return block_sum(x, red); }
+// sum over the 64 lanes of a wave; every lane of the wave must call; lane 0 holds the result
+__device__ __forceinline__ Fr wave_sum_fr(Fr x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        Fr y;
+#pragma unroll
+        for (int l = 0; l < 8; ++l) y.v[l] = __shfl_down(x.v[l], off, 64);
+        x = fr_add(x, y);
+    }
+    return x;
+}
 
+// The end of the combined sumcheck in one block: the i-tables at the full i-point, the
+// log2 J rounds over j, the finals, and the merge of the three claims on aux.
+//
+// With every i bound, the summand over j is
+//   a0 [L0 + B0 (a0 - 1)] + a1 [L1 + B1 (a1 - 1)],
+//   L0 = r^2 beta_Z(v) s + r beta_A(v)(1-sign(v)) s',   B0 = beta_I(v) beta_J,
+//   L1, B1 the same for slice 1 (with r'), a_k = aux~(k, v, j):
+// six tables of J entries.  Work is spread as (evaluation point, slice, j): wave w takes the
+// point x in {0, 2, 3}[w] and sums it by itself, so a round needs no cross-wave reduction.
 __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
-    __shared__ uint32_t red[64];
     __shared__ TsShared TS;
-    __shared__ Fr A0[64], A1[64], S[64], SP[64], BJ[64];   // tables over j
-    __shared__ Fr M[128], E[128];                           // merge tables over (k, j)
+    __shared__ Fr T6[6][64];                               // A0, A1, L0, L1, B0, B1 over j
+    __shared__ Fr S[64], SP[64];
+    __shared__ Fr M[128], E[128];                          // merge tables over (k, j)
     __shared__ Fr sc[LIN_TABLES];
     __shared__ Fr g[4];
     __shared__ Fr fin[3];
     __shared__ Fr rho[3];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     DevState* st = a.st;
     block_ts_load(TS, st);
     const int J = 1 << a.lj, nbits = a.q_bits + a.r_bits;
@@ -583,112 +625,119 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
 
     // scalars: the D-sized tables at the full i-point
     if (tid < LIN_TABLES) {
-        Fr lo = tab_ld(a.tabs.t[tid], 0);
         bool present = a.bin.has_ga || !(tid == T_BGA || tid == T_GA || tid == T_BGZ || tid == T_GAP);
-        if (!present) lo = fr_zero();
-        else if (a.li >= 1) {
-            Fr hi = tab_ld(a.tabs.t[tid], 1);
-            lo = fr_add(lo, fr_mul_ni(vlast, fr_sub(hi, lo)));
+        Fr lo = fr_zero();
+        if (present) {
+            lo = f9_to_fr(f9tab_ld(a.tabs.t[tid], 0));
+            if (a.li >= 1) {
+                Fr hi = f9_to_fr(f9tab_ld(a.tabs.t[tid], 1));
+                lo = fr_add(lo, fr_mul_ni(vlast, fr_sub(hi, lo)));
+            }
         }
         sc[tid] = lo;
-    }
-    // tables over j
-    if (tid < 64) {
-        const int j = tid;
-        Fr a0 = fr_zero(), a1 = fr_zero(), s = fr_zero(), sp = fr_zero(), bj = fr_zero();
-        if (j < J) bj = a.bin.bJ[j];
-        if (j < nbits) {
-            for (int k = 0; k < (a.bin.has_ga ? 2 : 1); ++k) {
-                Fr val;
-                if (a.li == 0) {
-                    const int64_t* src = k == 0 ? a.bin.z : a.bin.ga;
-                    val = (((uint64_t)src[0] >> j) & 1) ? one : fr_zero();
-                } else if (a.li == 1) {
-                    // one challenge: the entry interpolates the bits of the two integers
-                    const int64_t* src = k == 0 ? a.bin.z : a.bin.ga;
-                    const int code = (int)(((uint64_t)src[0] >> j) & 1) | (int)((((uint64_t)src[1] >> j) & 1) << 1);
-                    val = bit_pair_value(code, vlast, one);
-                } else {
-                    // the columns were written after the second challenge; later rounds folded them
-                    F9Tab col = aux_col9(a.bin, k, j);
-                    val = f9_to_fr(f9tab_ld(col, 0));
-                    if (a.li >= 3) {
-                        Fr hi = f9_to_fr(f9tab_ld(col, 1));
-                        val = fr_add(val, fr_mul_ni(vlast, fr_sub(hi, val)));
-                    }
+    } else if (tid >= 64 && tid < 192) {
+        // aux~(k, v, j) for k = wave - 1
+        const int j = lane, k = wave - 1;
+        Fr val = fr_zero();
+        if (j < nbits && (k == 0 || a.bin.has_ga)) {
+            const int64_t* src = k == 0 ? a.bin.z : a.bin.ga;
+            if (a.li == 0) {
+                val = (((uint64_t)src[0] >> j) & 1) ? one : fr_zero();
+            } else if (a.li == 1) {
+                // one challenge: the entry interpolates the bits of the two integers
+                const int code = (int)(((uint64_t)src[0] >> j) & 1) | (int)((((uint64_t)src[1] >> j) & 1) << 1);
+                val = bit_pair_value(code, vlast, one);
+            } else {
+                // the columns were written after the second challenge; later rounds folded them
+                F9Tab col = aux_col9(a.bin, k, j);
+                val = f9_to_fr(f9tab_ld(col, 0));
+                if (a.li >= 3) {
+                    Fr hi = f9_to_fr(f9tab_ld(col, 1));
+                    val = fr_add(val, fr_mul_ni(vlast, fr_sub(hi, val)));
                 }
-                if (k == 0) a0 = val;
-                else a1 = val;
             }
-            // s_{Q+R}(j) and s'(j) (Sec. 3.1, App. A)
+        }
+        T6[k][j] = val;
+        M[64 * k + j] = val;
+    } else if (tid >= 192) {
+        // s_{Q+R}(j) and s'(j) (Sec. 3.1, App. A)
+        const int j = lane;
+        Fr s = fr_zero(), sp = fr_zero();
+        if (j < nbits) {
             if (j < nbits - 1) s = fr_from_i64((int64_t)1 << j);
             else s = fr_from_i64(j == 63 ? INT64_MIN : -((int64_t)1 << j));
             if (j == a.r_bits - 1) sp = one;
             else if (j >= a.r_bits && j < nbits - 1) sp = fr_from_i64((int64_t)1 << (j - a.r_bits));
             else if (j == nbits - 1) sp = fr_from_i64(-((int64_t)1 << (a.q_bits - 1)));
         }
-        A0[j] = a0;
-        A1[j] = a1;
         S[j] = s;
         SP[j] = sp;
-        BJ[j] = bj;
-        M[j] = a0;
-        M[64 + j] = a1;
     }
     __syncthreads();
-    // coefficients that stay fixed during the j-rounds
-    const Fr cZ = sc[T_BZ];                          // r^2 beta_Z(v)
-    const Fr cA = fr_mul_ni(sc[T_BA], sc[T_NS]);        // r beta_A(v) (1 - sign(v))
-    const Fr cGA = sc[T_BGA];
-    const Fr cGZ = fr_mul_ni(sc[T_BGZ], sc[T_NS]);
-    const Fr cB0 = sc[T_BI];                         // beta_I(v)
-    const Fr cB1 = fr_mul_ni(st->weights[4], sc[T_BI]); // r' beta_I(v)
+    {
+        // L0, L1, B0, B1: one table per wave
+        const int j = lane;
+        const Fr ns = sc[T_NS];
+        Fr val = fr_zero();
+        if (j < J) {
+            if (wave == 0) val = fr_add(fr_mul_ni(sc[T_BZ], S[j]), fr_mul_ni(fr_mul_ni(sc[T_BA], ns), SP[j]));
+            else if (wave == 1) val = fr_add(fr_mul_ni(sc[T_BGA], S[j]), fr_mul_ni(fr_mul_ni(sc[T_BGZ], ns), SP[j]));
+            else if (wave == 2) val = fr_mul_ni(sc[T_BI], a.bin.bJ[j]);
+            else val = fr_mul_ni(fr_mul_ni(st->weights[4], sc[T_BI]), a.bin.bJ[j]);
+        }
+        T6[2 + wave][j] = val;
+    }
+    __syncthreads();
 
     int cur = J;
     for (int t = 0; t < a.lj; ++t) {
         const int half = cur >> 1;
-        Fr f[4];
-#pragma unroll
-        for (int x = 0; x < 4; ++x) f[x] = fr_zero();
-        if (tid < half) {
-            Fr a0[4], a1[4], s[4], sp[4], bj[4];
-            line4(A0[tid], A0[tid + half], a0);
-            line4(A1[tid], A1[tid + half], a1);
-            line4(S[tid], S[tid + half], s);
-            line4(SP[tid], SP[tid + half], sp);
-            line4(BJ[tid], BJ[tid + half], bj);
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                Fr lin0 = fr_add(fr_mul_ni(cZ, s[x]), fr_mul_ni(cA, sp[x]));
-                Fr lin1 = fr_add(fr_mul_ni(cGA, s[x]), fr_mul_ni(cGZ, sp[x]));
-                Fr q0 = fr_sub(fr_mul_ni(a0[x], a0[x]), a0[x]);
-                Fr q1 = fr_sub(fr_mul_ni(a1[x], a1[x]), a1[x]);
-                Fr binp = fr_mul_ni(bj[x], fr_add(fr_mul_ni(cB0, q0), fr_mul_ni(cB1, q1)));
-                f[x] = fr_add(fr_add(fr_mul_ni(lin0, a0[x]), fr_mul_ni(lin1, a1[x])), binp);
+        // wave w < 3: point x = 0, 2, 3; lane = (slice << 5) | j
+        Fr f = fr_zero();
+        const int k = lane >> 5, j = lane & 31;
+        if (wave < 3 && j < half) {
+            Fr av, lv, bv;
+            {
+                const Fr lo = T6[k][j], hi = T6[k][j + half];
+                const Fr lL = T6[2 + k][j], hL = T6[2 + k][j + half];
+                const Fr lB = T6[4 + k][j], hB = T6[4 + k][j + half];
+                if (wave == 0) {
+                    av = lo; lv = lL; bv = lB;
+                } else {
+                    const Fr da = fr_sub(hi, lo), dL = fr_sub(hL, lL), dB = fr_sub(hB, lB);
+                    av = fr_add(hi, da); lv = fr_add(hL, dL); bv = fr_add(hB, dB);
+                    if (wave == 2) {
+                        av = fr_add(av, da); lv = fr_add(lv, dL); bv = fr_add(bv, dB);
+                    }
+                }
             }
+            f = fr_mul_ni(av, fr_add(lv, fr_mul_ni(bv, fr_sub(av, one))));
         }
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            Fr s = block_sum(f[x], red);
-            if (tid == 0) g[x] = s;
+        if (wave < 3) {
+            f = wave_sum_fr(f);
+            if (lane == 0) g[wave == 0 ? 0 : wave + 1] = f;
         }
+        __syncthreads();
+        if (tid == 0) g[1] = fr_sub(st->claim, g[0]);
         __syncthreads();
         Fr v = block_finalise_round(TS, st, g, 4, a.rounds_off + (uint32_t)(a.li + t) * 128,
                                     a.chal_v + a.li + t);
-        if (tid < half) {
-            A0[tid] = fr_add(A0[tid], fr_mul_ni(v, fr_sub(A0[tid + half], A0[tid])));
-            A1[tid] = fr_add(A1[tid], fr_mul_ni(v, fr_sub(A1[tid + half], A1[tid])));
-            S[tid] = fr_add(S[tid], fr_mul_ni(v, fr_sub(S[tid + half], S[tid])));
-            SP[tid] = fr_add(SP[tid], fr_mul_ni(v, fr_sub(SP[tid + half], SP[tid])));
-            BJ[tid] = fr_add(BJ[tid], fr_mul_ni(v, fr_sub(BJ[tid + half], BJ[tid])));
+        // fold the six tables: thread = (table, j)
+        Fr folded = fr_zero();
+        const int tb = tid >> 5, fj = tid & 31;
+        if (tb < 6 && fj < half) {
+            const Fr lo = T6[tb][fj], hi = T6[tb][fj + half];
+            folded = fr_add(lo, fr_mul_ni(v, fr_sub(hi, lo)));
         }
+        __syncthreads();
+        if (tb < 6 && fj < half) T6[tb][fj] = folded;
         __syncthreads();
         cur = half;
     }
     // finals: aux~(0, v, wbar), aux~(1, v, wbar), aux~(0, v, Q+R-1) = 1 - (1 - sign)(v)
     if (tid == 0) {
-        fin[0] = A0[0];
-        fin[1] = A1[0];
+        fin[0] = T6[0][0];
+        fin[1] = T6[1][0];
         fin[2] = fr_sub(one, sc[T_NS]);
         for (int k = 0; k < 3; ++k) st->scal[4 + k] = fin[k];
     }
@@ -736,9 +785,8 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
         E[64 + tid] = tid < J ? fr_mul_ni(rho[1], bw) : fr_zero();
     }
     __syncthreads();
-    // merge sumcheck over (k, j): k first (pairs index c with 64 + c), then the lj
-    // variables of j inside the first J entries of each half
-    // Compact the tables to 2J entries when J < 64 so that halves are contiguous.
+    // merge sumcheck over (k, j): k first, then the variables of j.  Compact the tables to
+    // 2J entries when J < 64 so that halves are contiguous.
     if (J < 64) {
         Fr m1 = fr_zero(), e1 = fr_zero();
         if (tid < J) {
@@ -755,26 +803,30 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
     cur = 2 * J;
     for (int t = 0; t < 1 + a.lj; ++t) {
         const int half = cur >> 1;
-        Fr f[3];
-#pragma unroll
-        for (int x = 0; x < 3; ++x) f[x] = fr_zero();
-        if (tid < half) {
-            Fr mlo = M[tid], mhi = M[tid + half], elo = E[tid], ehi = E[tid + half];
-            Fr md = fr_sub(mhi, mlo), ed = fr_sub(ehi, elo);
-            f[0] = fr_mul_ni(mlo, elo);
-            f[1] = fr_mul_ni(mhi, ehi);
-            f[2] = fr_mul_ni(fr_add(mhi, md), fr_add(ehi, ed));
+        // wave w < 3: point x = w; lane = index below half (half <= 64)
+        Fr f = fr_zero();
+        if (wave < 3 && lane < half) {
+            const Fr mlo = M[lane], mhi = M[lane + half], elo = E[lane], ehi = E[lane + half];
+            if (wave == 0) f = fr_mul_ni(mlo, elo);
+            else if (wave == 1) f = fr_mul_ni(mhi, ehi);
+            else f = fr_mul_ni(fr_add(mhi, fr_sub(mhi, mlo)), fr_add(ehi, fr_sub(ehi, elo)));
         }
-#pragma unroll
-        for (int x = 0; x < 3; ++x) {
-            Fr s = block_sum(f[x], red);
-            if (tid == 0) g[x] = s;
+        if (wave < 3) {
+            f = wave_sum_fr(f);
+            if (lane == 0) g[wave] = f;
         }
         __syncthreads();
         Fr v = block_finalise_round(TS, st, g, 3, a.merge_rounds_off + (uint32_t)t * 96, a.chal_rho + 3 + t);
-        if (tid < half) {
-            M[tid] = fr_add(M[tid], fr_mul_ni(v, fr_sub(M[tid + half], M[tid])));
-            E[tid] = fr_add(E[tid], fr_mul_ni(v, fr_sub(E[tid + half], E[tid])));
+        Fr fm = fr_zero();
+        const int tb = tid >> 6;
+        if (tb < 2 && lane < half) {
+            const Fr lo = tb == 0 ? M[lane] : E[lane], hi = tb == 0 ? M[lane + half] : E[lane + half];
+            fm = fr_add(lo, fr_mul_ni(v, fr_sub(hi, lo)));
+        }
+        __syncthreads();
+        if (tb < 2 && lane < half) {
+            if (tb == 0) M[lane] = fm;
+            else E[lane] = fm;
         }
         __syncthreads();
         cur = half;
@@ -844,23 +896,31 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     // memory: 10 D-sized tables, beta_J, aux columns (2 * nbits columns of D/4 rows, 36 B entries)
     const uint64_t rows = D >= 4 ? D / 4 : 1;
     const uint64_t aux_elems = (uint64_t)(has_ga ? 2 : 1) * nbits * rows;
-    void* mem = zk_alloc(ctx, ((uint64_t)LIN_TABLES * D + 64) * 32 + (li >= 2 ? aux_elems * 36 : 0));
-    if (!mem) return ZKDL_ENOMEM;
+    void* mem = zk_alloc(ctx, (uint64_t)LIN_TABLES * D * 36 + 64 * 32 + (li >= 2 ? aux_elems * 36 : 0));
+    void* beta_mem = zk_alloc(ctx, (uint64_t)5 * D * 32);
+    if (!mem || !beta_mem) {
+        zk_free(ctx, mem);
+        zk_free(ctx, beta_mem);
+        return ZKDL_ENOMEM;
+    }
     uint32_t* base = (uint32_t*)mem;
     ZkTabs tabs;
     for (int k = 0; k < LIN_TABLES; ++k) {
-        tabs.t[k] = make_tab(base, D);
-        base += 8 * D;
+        tabs.t[k].p = base;
+        tabs.t[k].ps = D;
+        base += 9 * D;
     }
     Fr* bJ = (Fr*)base;
     base += 8 * 64;
     uint32_t* aux = base;
+    ZkBeta8 beta8;
+    for (int k = 0; k < 5; ++k) beta8.t[k] = make_tab((uint32_t*)beta_mem + (uint64_t)k * 8 * D, D);
 
-    int rc = zk_build_beta(ctx, st->chal + c_uz, li, tabs.t[T_BZ]);
-    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ua, li, tabs.t[T_BA]);
-    if (rc == ZKDL_OK && has_ga) rc = zk_build_beta(ctx, st->chal + c_uga, li, tabs.t[T_BGA]);
-    if (rc == ZKDL_OK && has_ga) rc = zk_build_beta(ctx, st->chal + c_ugz, li, tabs.t[T_BGZ]);
-    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ubin, li, tabs.t[T_BI]);
+    int rc = zk_build_beta(ctx, st->chal + c_uz, li, beta8.t[0]);
+    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ua, li, beta8.t[1]);
+    if (rc == ZKDL_OK && has_ga) rc = zk_build_beta(ctx, st->chal + c_uga, li, beta8.t[2]);
+    if (rc == ZKDL_OK && has_ga) rc = zk_build_beta(ctx, st->chal + c_ugz, li, beta8.t[3]);
+    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ubin, li, beta8.t[4]);
     // beta_J as an array of structures: one plane of J elements read through FrTab, then copied
     void* bj_tmp = zk_alloc(ctx, 64 * 32);
     if (!bj_tmp) rc = ZKDL_ENOMEM;
@@ -869,6 +929,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     if (rc != ZKDL_OK) {
         zk_free(ctx, bj_tmp);
         zk_free(ctx, mem);
+        zk_free(ctx, beta_mem);
         return rc;
     }
     zk_launch_soa_to_aos(ctx, bj_soa, J, bJ);
@@ -879,6 +940,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     pa.D = D;
     pa.nbits = nbits;
     pa.r_bits = R;
+    pa.beta = beta8;
     pa.tabs = tabs;
     pa.part = ctx->partials;
     pa.st = st;
@@ -892,7 +954,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     ca.claim0_off = claim0_off;
     ca.chal_r = c_r;
     hipLaunchKernelGGL(k_zk_claims, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ca);
-    hipLaunchKernelGGL(k_zk_scale, dim3(blocks_for(D, 65536)), dim3(ZK_BLOCK), 0, ctx->stream, tabs, D,
+    hipLaunchKernelGGL(k_zk_scale, dim3(blocks_for(D, 65536)), dim3(ZK_BLOCK), 0, ctx->stream, beta8, tabs, D,
                        (const Fr*)st->weights, has_ga);
 
     BinArgs ba;
@@ -985,5 +1047,6 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     hipLaunchKernelGGL(k_zk_tail, dim3(1), dim3(TAIL_THREADS), 0, ctx->stream, ta);
     zk_free(ctx, bj_tmp);
     zk_free(ctx, mem);
+    zk_free(ctx, beta_mem);
     return ZKDL_OK;
 }
