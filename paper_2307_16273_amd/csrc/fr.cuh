@@ -284,6 +284,60 @@ FR_HD Fr f9_to_fr(const F9& a) {
     return fr_pack(f9_cond_sub(f9_mul(fr_unpack(fr_const(frc::ONE)), f9_norm(a))));
 }
 
+// ---- wide accumulation: sum of many products, one Montgomery reduction at the end ----
+// cols[k] collects the weight-2^(29k) terms of sum_n a_n * b_n (64-bit unsigned columns).
+
+// cols += a * b for normal a, b: 81 multiply-adds, no carries.  Each column gains at most
+// 9 * 2^58; renormalise (f9_cols_norm) after every fourth product.
+FR_HD void f9_cols_mac(uint64_t cols[17], const F9& a, const F9& b) {
+#pragma unroll
+    for (int i = 0; i < 9; ++i)
+#pragma unroll
+        for (int j = 0; j < 9; ++j) cols[i + j] += (uint64_t)a.v[i] * b.v[j];
+}
+
+// cols += a * x for a normal a and a 32-bit unsigned x: nine multiply-adds into columns
+// 0..8, each gaining below 2^61; renormalise after every fourth product.
+FR_HD void f9_cols_mac_small(uint64_t cols[17], const F9& a, uint32_t x) {
+#pragma unroll
+    for (int i = 0; i < 9; ++i) cols[i] += (uint64_t)a.v[i] * x;
+}
+
+// carry propagation over the first n columns: same value, columns 0..n-2 below 2^29
+template <int N>
+FR_HD void f9_cols_norm(uint64_t cols[17]) {
+#pragma unroll
+    for (int k = 0; k + 1 < N; ++k) {
+        cols[k + 1] += cols[k] >> 29;
+        cols[k] &= frc::M29;
+    }
+}
+
+// Montgomery reduction of a column sum: (V + m r) / 2^261 for V = sum_k cols[k] 2^(29k),
+// columns below 2^62.  Normal result below V / 2^261 + r.
+FR_HD F9 f9_redc(const uint64_t cols[17]) {
+    uint64_t acc = 0;
+    uint32_t m[9];
+    F9 t;
+#pragma unroll
+    for (int k = 0; k < 17; ++k) {
+        const int lo_i = k < 9 ? 0 : k - 8, hi_i = k < 9 ? k : 8;
+        acc += cols[k];
+#pragma unroll
+        for (int i = lo_i; i <= hi_i; ++i)
+            if (k - i >= 1) acc += (uint64_t)m[i] * frc::MOD9[k - i];
+        if (k < 9) {
+            m[k] = (0u - (uint32_t)acc) & frc::M29;
+            acc += m[k];
+        } else {
+            t.v[k - 9] = (uint32_t)acc & frc::M29;
+        }
+        acc >>= 29;
+    }
+    t.v[8] = (uint32_t)acc;
+    return t;
+}
+
 FR_HD F9 f9_zero() {
     F9 z;
 #pragma unroll

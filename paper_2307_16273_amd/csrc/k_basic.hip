@@ -37,6 +37,9 @@ static unsigned grid_for(uint64_t n, unsigned cap = 65536) {
     return (unsigned)b;
 }
 
+// the column sums of the lazy partial-evaluation kernels stay in range for this many elements per thread
+constexpr uint64_t PE_LAZY_MAX_CHUNK = 4096;
+
 void zk_launch_convert(zkdl_ctx* ctx, const void* src, int kind, uint64_t n, FrTab out) {
     unsigned g = grid_for(n);
     if (kind == TK_I32)
@@ -215,6 +218,120 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_pe_inner(PeArgs p) {
     }
 }
 
+// Lazy variants: the products of one output are summed as 64-bit columns of 29-bit limb
+// products and reduced once (f9_cols_*, f9_redc), instead of one Montgomery product and one
+// modular addition per source element.  Thread per output element (o, i); blockIdx.y selects
+// the chunk of the contracted axis; beta_a is the same for every thread of an iteration.
+//
+// Fr source: sum_a beta_a T_a, 81 multiply-adds per element, both in Montgomery form, so the
+// reduced sum is the Montgomery form of the result.
+// int32 source: x_a is a plain integer: 9 multiply-adds per element into a positive or a
+// negative column set by the sign of x_a; V = P - N is already "beta times integer", so each
+// side is reduced (divide by 2^261) and multiplied back by 2^522 mod r.
+template <int KIND>
+__global__ __launch_bounds__(ZK_BLOCK) void k_pe_mid_lazy(PeArgs p) {
+    const uint64_t n_out = p.O * p.I;
+    const uint64_t a0 = (uint64_t)blockIdx.y * p.a_chunk;
+    uint64_t a1 = a0 + p.a_chunk;
+    if (a1 > p.A) a1 = p.A;
+    for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < n_out;
+         e += (uint64_t)gridDim.x * blockDim.x) {
+        const uint64_t o = e / p.I, i = e - o * p.I;
+        Fr res;
+        if (KIND == TK_FR) {
+            uint64_t c[17];
+#pragma unroll
+            for (int k = 0; k < 17; ++k) c[k] = 0;
+            int pending = 0;
+#pragma unroll 2
+            for (uint64_t a = a0; a < a1; ++a) {
+                const F9 b9 = fr_unpack(tab_ld(p.beta, a));
+                const F9 x9 = fr_unpack(tab_ld(p.fr_src, (o * p.A + a) * p.I + i));
+                f9_cols_mac(c, b9, x9);
+                if (++pending == 4) {
+                    pending = 0;
+                    f9_cols_norm<17>(c);
+                }
+            }
+            f9_cols_norm<17>(c);
+            res = f9_to_fr(f9_norm_reduce(f9_redc(c)));
+        } else {
+            uint64_t cp[17], cn[17];
+#pragma unroll
+            for (int k = 0; k < 17; ++k) cp[k] = cn[k] = 0;
+            int pending = 0;
+            const int32_t* src = (const int32_t*)p.src;
+            for (uint64_t a = a0; a < a1; ++a) {
+                const F9 b9 = fr_unpack(tab_ld(p.beta, a));
+                const int32_t x = src[(o * p.A + a) * p.I + i];
+                const uint32_t xp = x > 0 ? (uint32_t)x : 0u, xn = x < 0 ? (uint32_t)0 - (uint32_t)x : 0u;
+                f9_cols_mac_small(cp, b9, xp);
+                f9_cols_mac_small(cn, b9, xn);
+                if (++pending == 4) {
+                    pending = 0;
+                    f9_cols_norm<10>(cp);
+                    f9_cols_norm<10>(cn);
+                }
+            }
+            f9_cols_norm<10>(cp);
+            f9_cols_norm<10>(cn);
+            const F9 r2 = fr_unpack(fr_const(frc::R2));
+            const F9 mp = f9_mul(f9_redc(cp), r2), mn = f9_mul(f9_redc(cn), r2);   // both normal, below 2r
+            res = f9_to_fr(f9_sub(mp, mn));
+        }
+        tab_st(p.out, (uint64_t)blockIdx.y * n_out + e, res);
+    }
+}
+
+// Innermost axis contracted, int32 source: one wave per tile of 64 output rows and one chunk
+// of the axis.  The tile of integers is read row by row (each row segment is contiguous, so
+// the loads coalesce) and transposed through LDS; then lane = row, and beta_a is the same for
+// all lanes of an iteration.  Same column arithmetic as k_pe_mid_lazy<TK_I32>.
+__global__ __launch_bounds__(64) void k_pe_inner_i32_lazy(PeArgs p) {
+    __shared__ int32_t tile[64][65];
+    __shared__ F9 sb[64];
+    const int lane = threadIdx.x;
+    const uint64_t row0 = (uint64_t)blockIdx.x * 64;
+    const uint64_t a0 = (uint64_t)blockIdx.y * p.a_chunk;
+    uint64_t a1 = a0 + p.a_chunk;
+    if (a1 > p.A) a1 = p.A;
+    const int32_t* src = (const int32_t*)p.src;
+    uint64_t cp[17], cn[17];
+#pragma unroll
+    for (int k = 0; k < 17; ++k) cp[k] = cn[k] = 0;
+    int pending = 0;
+    const uint64_t rows_here = p.O - row0 < 64 ? p.O - row0 : 64;
+    for (uint64_t at = a0; at < a1; at += 64) {
+        const int na = (int)(a1 - at < 64 ? a1 - at : 64);
+        if (lane < na) sb[lane] = fr_unpack(tab_ld(p.beta, at + lane));
+        for (uint64_t r = 0; r < rows_here; ++r)
+            if (lane < na) tile[r][lane] = src[(row0 + r) * p.A + at + lane];
+        __syncthreads();
+        if ((uint64_t)lane < rows_here) {
+            for (int k = 0; k < na; ++k) {
+                const int32_t x = tile[lane][k];
+                const F9 b9 = sb[k];
+                const uint32_t xp = x > 0 ? (uint32_t)x : 0u, xn = x < 0 ? (uint32_t)0 - (uint32_t)x : 0u;
+                f9_cols_mac_small(cp, b9, xp);
+                f9_cols_mac_small(cn, b9, xn);
+                if (++pending == 4) {
+                    pending = 0;
+                    f9_cols_norm<10>(cp);
+                    f9_cols_norm<10>(cn);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if ((uint64_t)lane < rows_here) {
+        f9_cols_norm<10>(cp);
+        f9_cols_norm<10>(cn);
+        const F9 r2 = fr_unpack(fr_const(frc::R2));
+        const F9 mp = f9_mul(f9_redc(cp), r2), mn = f9_mul(f9_redc(cn), r2);
+        tab_st(p.out, (uint64_t)blockIdx.y * p.O + row0 + lane, f9_to_fr(f9_sub(mp, mn)));
+    }
+}
+
 // out[e] = sum_c part[c * n + e]
 __global__ __launch_bounds__(ZK_BLOCK) void k_sum_chunks(FrTab part, uint64_t n, uint64_t chunks,
                                                          FrTab out) {
@@ -230,6 +347,8 @@ template <int KIND>
 static void launch_pe(zkdl_ctx* ctx, bool inner, const PeArgs& p, dim3 grid) {
     if (inner)
         hipLaunchKernelGGL(k_pe_inner<KIND>, grid, dim3(ZK_BLOCK), 0, ctx->stream, p);
+    else if ((KIND == TK_FR || KIND == TK_I32) && p.a_chunk <= PE_LAZY_MAX_CHUNK)
+        hipLaunchKernelGGL(k_pe_mid_lazy<KIND>, grid, dim3(ZK_BLOCK), 0, ctx->stream, p);
     else
         hipLaunchKernelGGL(k_pe_mid<KIND>, grid, dim3(ZK_BLOCK), 0, ctx->stream, p);
 }
@@ -246,10 +365,40 @@ int zk_partial_eval(zkdl_ctx* ctx, int kind, const void* src, uint64_t O, uint64
     p.I = I;
     uint64_t n_out = O * I;
     const bool inner = (I == 1);
-    // split the contracted axis until there is enough parallel work (~64k threads)
+    if (inner && kind == TK_I32 && A >= 64) {
+        // row tiles of 64 outputs x chunks of the axis, about a thousand single-wave blocks
+        const uint64_t tiles = (O + 63) / 64;
+        uint64_t chunks = 1;
+        while (tiles * chunks < 1024 && A / (chunks * 2) >= 64) chunks *= 2;
+        while (A / chunks > PE_LAZY_MAX_CHUNK) chunks *= 2;
+        if (tiles <= 0x7fffffffu && chunks <= 65535) {
+            p.a_chunk = (A + chunks - 1) / chunks;
+            void* tmp = nullptr;
+            if (chunks > 1) {
+                tmp = zk_alloc(ctx, chunks * n_out * 32);
+                if (!tmp) return ZKDL_ENOMEM;
+                p.out = make_tab(tmp, chunks * n_out);
+            } else {
+                p.out = out;
+            }
+            zk_prof_begin(ctx, ZKDL_PROF_PARTIAL_EVAL, 4.0 * (double)O * (double)A + 32.0 * (double)A + 32.0 * (double)n_out);
+            hipLaunchKernelGGL(k_pe_inner_i32_lazy, dim3((unsigned)tiles, (unsigned)chunks), dim3(64), 0, ctx->stream, p);
+            zk_prof_end(ctx);
+            if (chunks > 1) {
+                hipLaunchKernelGGL(k_sum_chunks, dim3(grid_for(n_out)), dim3(ZK_BLOCK), 0, ctx->stream, p.out,
+                                   n_out, chunks, out);
+                zk_free(ctx, tmp);
+            }
+            return ZKDL_OK;
+        }
+    }
+    // split the contracted axis until there is enough parallel work: the thread-per-output
+    // kernels hide their load latency only with several waves per SIMD (~256k threads)
     uint64_t units = inner ? n_out * 64 : n_out;
     uint64_t chunks = 1;
-    while (units * chunks < 65536 && chunks * 2 <= A && (A / (chunks * 2)) >= (inner ? 64u : 4u)) chunks *= 2;
+    const uint64_t want_units = inner ? 65536 : 262144;
+    while (units * chunks < want_units && chunks * 2 <= A && (A / (chunks * 2)) >= (inner ? 64u : 4u)) chunks *= 2;
+    while (!inner && A / chunks > PE_LAZY_MAX_CHUNK && chunks < 32768) chunks *= 2;
     p.a_chunk = (A + chunks - 1) / chunks;
     void* tmp = nullptr;
     if (chunks > 1) {

@@ -276,3 +276,28 @@ def test_config1_fc_layer_plus_relu(lib, ctx):
     from oracle.mle import mle_eval
     pts = g1["points"]
     assert g1["claims"][0] == mle_eval(fr_array(lay["Z"]), pts[:4 + 8])
+
+
+@pytest.mark.parametrize("shape,lo,hi", [((4096, 256), 0, 1), ((2, 8192, 64), 1, 2), ((512, 1024), 1, 2),
+                                          ((96 // 96 * 128, 4096), 1, 2), ((3 * 0 + 64, 64), 1, 2)])
+def test_partial_eval_long_axes_int32_and_fr(lib, ctx, shape, lo, hi):
+    """Long contracted axes go through the wide-accumulation kernels: extreme and sign-mixed integers."""
+    import torch
+    say(f"partial_eval long axis shape={shape} axes=[{lo},{hi})")
+    rng = np.random.default_rng(sum(shape))
+    n = int(np.prod(shape))
+    src = rng.integers(-2 ** 31, 2 ** 31, n, dtype=np.int64).astype(np.int32)
+    src[:8] = [-2 ** 31, 2 ** 31 - 1, -1, 0, 1, -2 ** 31, -2 ** 31, 2 ** 31 - 1]
+    npt = sum(int(s).bit_length() - 1 for s in shape[lo:hi])
+    point = fr_array_from_le(rand_fr_bytes(5, npt), npt).tolist()
+    t = lib.tensor_wrap_int(ctx, torch.from_numpy(src).cuda(), shape)
+    out = lib.mle_partial_eval(ctx, t, lo, hi, point)
+    expect, oshape = partial_eval(fr_array(src), shape, lo, hi, point)
+    assert out.download() == array_to_le(expect)
+    if lo == 0:
+        raw = uniform_fr_limbs(rng, n)
+        raw[0] = [0xFFFFFFFF00000000, 0x53BDA402FFFE5BFE, 0x3339D80809A1D805, 0x73EDA753299D7D48]   # r - 1
+        tf = lib.fr_tensor_upload(ctx, raw.tobytes(), shape)
+        outf = lib.mle_partial_eval(ctx, tf, lo, hi, point)
+        expf, _ = partial_eval(fr_array_from_le(raw.tobytes(), n), shape, lo, hi, point)
+        assert outf.download() == array_to_le(expf)
