@@ -166,6 +166,20 @@ def main():
         out["config"]["proof_ms_batch64_8layer_step_min"] = 1e3 * ag_min
         out["config"]["paper_context"] = ("paper: < 1 s per batch-64 update, 8-layer 10M-parameter net, one "
                                           "Tesla A100, whole protocol including commitments (not comparable)")
+        del dw
+        # the two larger aggregation windows of the config list, for reference
+        for key, (nl, wd, bs, st, cfg) in {"config4_16steps": (8, 1024, 64, 16, 4),
+                                           "config5_4x4096_b256": (4, 4096, 256, 1, 5)}.items():
+            wit = fcnn_window(CONFIG_SEED + cfg, n_layers=nl, width=wd, batch=bs, steps=st)
+            dw = {k: wit[k] for k in ("L", "B", "width", "T", "Q", "R")}
+            for k in ("A", "W", "GZ", "Zr", "GA"):
+                dw[k] = torch.from_numpy(np.ascontiguousarray(wit[k])).cuda()
+            med, _ = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + cfg)), 3)
+            out["config"]["proof_ms_" + key] = 1e3 * med
+            if st > 1:
+                out["config"]["proof_ms_" + key + "_per_step"] = 1e3 * med / st
+            del dw, wit
+            ctx.trim()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_log2_size)
     print(json.dumps(out))

@@ -301,3 +301,88 @@ def test_partial_eval_long_axes_int32_and_fr(lib, ctx, shape, lo, hi):
         outf = lib.mle_partial_eval(ctx, tf, lo, hi, point)
         expf, _ = partial_eval(fr_array_from_le(raw.tobytes(), n), shape, lo, hi, point)
         assert outf.download() == array_to_le(expf)
+
+
+def test_full_size_microbench_sumcheck_by_properties(lib, ctx):
+    """Three tables of 2^24 (the benchmark's launch configuration).  The oracle cannot redo
+    the proof in seconds at this size, so the proof is checked through what holds at any size:
+    the oracle's verifier accepts it (every round, the final product, the same transcript),
+    claim_0 equals the exact integer sum, and the finals equal closed-form MLE evaluations of
+    tables chosen to have one: T0[b] = b, T1[b] = 3b + 7, T2[b] = b xor c."""
+    import torch
+    say("full-size sumcheck_product (2^24 x 3)")
+    d = 24
+    n = 1 << d
+    c = 0xA5C3F1
+    b = np.arange(n, dtype=np.int64)
+    tabs_np = [b, 3 * b + 7, b ^ c]
+    tabs = [lib.fr_tensor_upload(ctx, torch.from_numpy(t).cuda(), (n,)) for t in tabs_np]
+    tr = lib.Transcript(99)
+    got = lib.sumcheck_product(ctx, tabs, tr)
+    ots = OracleTranscript(99)
+    proof, vs = P.product_verify(got["proof"], 3, d, ots)
+    assert tr.digest() == ots.digest() and got["points"] == vs
+    # claim_0: exact sum of the integer products (chunked so that intermediate values stay exact)
+    total = 0
+    for s in range(0, n, 1 << 20):
+        x = b[s:s + (1 << 20)].astype(object)
+        total += int(np.sum(x * (3 * x + 7) * (x ^ c)))
+    assert proof.claim0 == total % R_MOD
+    # finals: the MLE of b is sum_k 2^(d-1-k) v_k; xor with a constant flips v_k to 1 - v_k
+    idx = sum(((1 << (d - 1 - k)) * vs[k]) for k in range(d)) % R_MOD
+    xor = sum((1 << (d - 1 - k)) * ((1 - vs[k]) if (c >> (d - 1 - k)) & 1 else vs[k]) for k in range(d)) % R_MOD
+    assert got["claims"] == [idx, (3 * idx + 7) % R_MOD, xor]
+
+
+def test_full_size_partial_eval_sampled(lib, ctx):
+    """4096 x 4096 uniform Fr matrix at a row point: sampled output columns against the oracle."""
+    say("full-size mle_partial_eval (4096 x 4096)")
+    rng = np.random.default_rng(CONFIG_SEED + 2)
+    side = 4096
+    limbs = uniform_fr_limbs(rng, side * side)
+    t = lib.fr_tensor_upload(ctx, limbs, (side, side))
+    point = fr_array_from_le(rand_fr_bytes(8, 12), 12).tolist()
+    out = lib.mle_partial_eval(ctx, t, 0, 1, point).download()
+    from oracle.mle import beta_table
+    beta = beta_table(point)
+    m3 = limbs.reshape(side, side, 4)
+    for col in (0, 1, 63, 64, 2047, 4095, 1234, 3001):
+        colv = fr_array_from_le(np.ascontiguousarray(m3[:, col, :]).tobytes(), side)
+        expect = int(np.sum(beta * colv) % R_MOD)
+        assert int.from_bytes(out[32 * col:32 * col + 32], "little") == expect
+
+
+def test_config3_aggregate_by_properties(lib, ctx):
+    """8 layers x 1024, batch 64 (the aggregate timed by the benchmark): the oracle's verifier
+    accepts the proof and ends in the same transcript state; the forward family's claim on the
+    activation stack equals its direct MLE evaluation."""
+    say("config 3 aggregate (8 x 1024^2, batch 64)")
+    from oracle.mle import mle_eval
+    wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)
+    tr = lib.Transcript(CONFIG_SEED + 3)
+    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr)
+    ots = OracleTranscript(CONFIG_SEED + 3)
+    res = P.aggregate_verify(got["proof"], ots)
+    assert tr.digest() == ots.digest()
+    assert got["points"] == ots.challenges
+    fproof, fpts = res["fwd"]
+    vn, vi = fpts["v"][:3], fpts["v"][3:]
+    assert fproof.finals[1] == mle_eval(fr_array(wit["A"]), vn + fpts["u0"] + vi)
+
+
+@pytest.mark.parametrize("name,layers,width,batch,steps,cfg", [
+    ("config 4: 8 x 1024^2, batch 64, 16 steps aggregated", 8, 1024, 64, 16, 4),
+    ("config 5: 4 x 4096^2, batch 256", 4, 4096, 256, 1, 5),
+])
+def test_large_aggregates_by_properties(lib, ctx, name, layers, width, batch, steps, cfg):
+    """Full-size aggregated proofs: the oracle's verifier replays every round of all four
+    families and must end in the library's transcript state."""
+    say(name)
+    wit = fcnn_window(CONFIG_SEED + cfg, n_layers=layers, width=width, batch=batch, steps=steps)
+    tr = lib.Transcript(CONFIG_SEED + cfg)
+    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr)
+    ots = OracleTranscript(CONFIG_SEED + cfg)
+    P.aggregate_verify(got["proof"], ots)
+    assert tr.digest() == ots.digest()
+    assert got["points"] == ots.challenges
+    ctx.trim()

@@ -43,12 +43,15 @@ def fc_relu_layer(seed, batch=16, width=256):
     return dict(X=x.astype(np.int32), W=w.astype(np.int32), Z=z)
 
 
-def fcnn_window(seed, n_layers, width, batch, steps=1, lr_shift=8, q_bits=32, r_bits=SCALE_BITS):
+def fcnn_window(seed, n_layers, width, batch, steps=1, lr_shift=None, q_bits=32, r_bits=SCALE_BITS):
     """T' = `steps` consecutive SGD steps of an L-layer width x width network.
 
     Step t draws its batch A^(0) ~ U[0,1) and output gradient dL/dY ~ N(0, 1e-2)
-    (variance) from default_rng(seed + t); weights ~ N(0, 2/width) from
-    default_rng(seed) before step 0.  Between steps W <- W - rescale(G_W, 16 + lr_shift).
+    (variance) from default_rng(seed + 1 + t); weights ~ N(0, 2/width) from
+    default_rng(seed) before step 0.  Between steps W <- W - rescale(G_W, 16 + lr_shift);
+    by default lr_shift = 8 + log2(batch): learning rate 2^-8 on the batch-mean gradient
+    (with the summed gradient the random output gradients make the weights, and then the
+    activations, leave the 32-bit range within a few steps).
     Returns stacks with slot n = t L + (l-1):
       A  int32 [N,B,w]  input of layer l (A^(l-1))
       W  int32 [N,w,w]  weights of layer l at step t
@@ -56,6 +59,8 @@ def fcnn_window(seed, n_layers, width, batch, steps=1, lr_shift=8, q_bits=32, r_
       Zr int64 [N,B,w]  Z^(l) where a ReLU follows (l < L), else 0
       GA int64 [N,B,w]  gradient of A^(l) before rescaling (l < L), else 0
     """
+    if lr_shift is None:
+        lr_shift = 8 + int(batch).bit_length() - 1
     wrng = np.random.default_rng(seed)
     weights = [quantise(wrng.normal(0.0, np.sqrt(2.0 / width), (width, width)))
                for _ in range(n_layers)]
