@@ -132,7 +132,7 @@ def main():
     pairs = fused["bytes"] / 576.0            # K = 3: 576 algorithmic bytes per pair index
     mad_rate = pairs * MODMUL_PER_PAIR_K3 * MADS_PER_MODMUL / (fused["ms"] * 1e-3) / 1e12 if fused["ms"] > 0 else 0.0
     roofline = {
-        "kernel": "k_sc_round<3,true> (fused fold-and-evaluate round)",
+        "kernel": "k_sc_round<3,1> and <3,2> (fused fold-and-evaluate rounds)",
         "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
         "traffic": traffic_from_profiles(),
         "launches": fused["launches"], "avg_launch_us": 1e3 * fused["ms"] / max(fused["launches"], 1),
