@@ -20,7 +20,7 @@ HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E, published
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one 32x32+64-bit multiply-add per lane and clock
 MAD_PEAK_T = 256 * 4 * 16 * 2.4e9 / 1e12
 MADS_PER_MODMUL = 153                       # 81 operand + 72 reduction products on 9 x 29-bit limbs
-MODMUL_PER_PAIR_K3 = 14                     # fused round, K = 3: 6 folds + 8 products
+MODMUL_PER_PAIR_K3 = 12                     # fused round, K = 3: 6 folds + 3 points x 2 products (g(1) is derived)
 
 
 def traffic_from_profiles():

@@ -82,6 +82,16 @@ class SumcheckProof:
         return SumcheckProof(k, deg, claim0, rs, finals), off
 
 
+def round_message(g):
+    """What a round binds into the transcript: g_t(0), g_t(2), ..., g_t(deg).
+
+    g_t(1) is left out: the round check g_t(0) + g_t(1) = claim (Sec. 2.2) fixes it,
+    and the claim is a function of what the transcript already holds.  The proof
+    bytes still carry all deg + 1 evaluations.
+    """
+    return [g[0]] + list(g[2:])
+
+
 def prove(tables, terms, degree, ts, absorb_claim=True, report=None):
     """Run the prover.  `tables`: list of equal-length object arrays (2^d);
     `terms`: list of (coef, [table ids]); returns (SumcheckProof, challenges).
@@ -107,7 +117,7 @@ def prove(tables, terms, degree, ts, absorb_claim=True, report=None):
             at_x = [(l + x * (h - l)) % R_MOD for l, h in zip(lo, hi)]
             g.append(hypercube_sum(at_x, terms))
         assert (g[0] + g[1]) % R_MOD == claim, "round invariant broken"
-        ts.absorb_fr(b"g", g)
+        ts.absorb_fr(b"g", round_message(g))
         v = ts.challenge()
         tables = [(l + v * (h - l)) % R_MOD for l, h in zip(lo, hi)]
         claim = lagrange_eval(g, v)
@@ -136,7 +146,7 @@ def verify_rounds(proof, ts, absorb_claim=True, expected_claim0=None):
     for g in proof.rounds:
         assert len(g) == proof.degree + 1
         assert (g[0] + g[1]) % R_MOD == claim, "g(0)+g(1) != claim"
-        ts.absorb_fr(b"g", g)
+        ts.absorb_fr(b"g", round_message(g))
         v = ts.challenge()
         claim = lagrange_eval(g, v)
         vs.append(v)

@@ -5,16 +5,25 @@ element after every round polynomial (App. B, both protocols).  Here each such
 message is replaced by a hash of everything sent so far.  The byte format is
 this build's own; the HIP library implements the same format independently.
 
-  state_0           = SHA256("zkdl-mi355x/v1" || u64le(seed))
-  absorb(label, m)  : state <- SHA256(state || u8(len label) || label || u64le(len m) || m)
-  challenges(n)     : for i < n: d0 = SHA256(state || 0x00 || u32le(i)),
-                                 d1 = SHA256(state || 0x01 || u32le(i)),
-                                 c_i = int_le(d0 || d1) mod r
-                      then state <- SHA256(state || 0x02)   (n = 0: nothing happens)
-  challenge()       = challenges(1)[0]
+The transcript is ONE byte stream, always a whole number of 64-byte blocks, and
+everything derived from it is a plain SHA-256 of a prefix-extension of it:
 
-The n challenges of one draw depend on the state only, so a point u in F^m is
-one hash latency on a parallel machine, not m.
+  stream_0          = "zkdl-mi355x/v2" zero-padded to 56 bytes || u64le(seed)      (one block)
+  absorb(label, m)  : stream <- stream || pad64(u8(len label) || label || u64le(len m) || m)
+                      (pad64: zero bytes up to the next multiple of 64; len label <= 32)
+  challenges(n)     : for i < n: d0 = SHA256(stream || 0xF0 || u32le(i)),
+                                 d1 = SHA256(stream || 0xF1 || u32le(i)),
+                                 c_i = int_le(d0 || d1) mod r
+                      then stream <- stream || 0xF2 || 63 zero bytes   (n = 0: nothing happens)
+  challenge()       = challenges(1)[0]
+  digest()          = SHA256(stream)
+
+Because the stream is block-aligned, a prover needs the SHA-256 chaining value
+after the last block only: an absorb costs one compression per 64 bytes of
+message, and each hash of a draw is one more compression from that chaining
+value (its block holds the five bytes and the padding), all of them independent.
+The n challenges of one draw are therefore one hash latency on a parallel
+machine, not n.
 
 Field elements are absorbed as 32-byte canonical little-endian strings.
 Test infrastructure; not used by the product.
@@ -24,21 +33,22 @@ import struct
 
 from .field import R_MOD, to_le
 
-DOMAIN = b"zkdl-mi355x/v1"
+DOMAIN = b"zkdl-mi355x/v2"
+MAX_LABEL = 32
 
 
 class Transcript:
     def __init__(self, seed=0):
-        self.state = hashlib.sha256(DOMAIN + struct.pack("<Q", seed)).digest()
+        self._h = hashlib.sha256()
+        self._h.update(DOMAIN + b"\x00" * (56 - len(DOMAIN)) + struct.pack("<Q", seed))
         self.challenges = []          # every challenge drawn, in order
 
     def absorb(self, label, data):
         label = bytes(label)
         data = bytes(data)
-        assert len(label) < 256
-        self.state = hashlib.sha256(
-            self.state + bytes([len(label)]) + label + struct.pack("<Q", len(data)) + data
-        ).digest()
+        assert len(label) <= MAX_LABEL
+        frame = bytes([len(label)]) + label + struct.pack("<Q", len(data)) + data
+        self._h.update(frame + b"\x00" * (-len(frame) % 64))
 
     def absorb_fr(self, label, elements):
         self.absorb(label, b"".join(to_le(e) for e in elements))
@@ -46,15 +56,18 @@ class Transcript:
     def absorb_u32(self, label, words):
         self.absorb(label, b"".join(struct.pack("<I", w) for w in words))
 
+    def _fork(self, tail):
+        f = self._h.copy()
+        f.update(tail)
+        return f.digest()
+
     def challenges_vec(self, n):
         out = []
         for i in range(n):
             idx = struct.pack("<I", i)
-            d0 = hashlib.sha256(self.state + b"\x00" + idx).digest()
-            d1 = hashlib.sha256(self.state + b"\x01" + idx).digest()
-            out.append(int.from_bytes(d0 + d1, "little") % R_MOD)
+            out.append(int.from_bytes(self._fork(b"\xf0" + idx) + self._fork(b"\xf1" + idx), "little") % R_MOD)
         if n > 0:
-            self.state = hashlib.sha256(self.state + b"\x02").digest()
+            self._h.update(b"\xf2" + b"\x00" * 63)
         self.challenges.extend(out)
         return out
 
@@ -62,4 +75,4 @@ class Transcript:
         return self.challenges_vec(1)[0]
 
     def digest(self):
-        return self.state
+        return self._h.digest()

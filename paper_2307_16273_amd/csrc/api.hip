@@ -263,12 +263,7 @@ extern "C" int zkdl_transcript_create(zkdl_transcript** out, uint64_t seed) {
     if (!out) return ZKDL_EINVAL;
     zkdl_transcript* t = new (std::nothrow) zkdl_transcript();
     if (!t) return ZKDL_ENOMEM;
-    static const char dom[] = "zkdl-mi355x/v1";
-    uint8_t buf[64];
-    uint32_t p = 0;
-    for (size_t i = 0; i < sizeof(dom) - 1; ++i) buf[p++] = (uint8_t)dom[i];
-    for (int i = 0; i < 8; ++i) buf[p++] = (uint8_t)(seed >> (8 * i));
-    sha::digest_inplace(buf, p, t->state);
+    ts::init(t->s, seed);
     *out = t;
     return ZKDL_OK;
 }
@@ -280,23 +275,22 @@ extern "C" int zkdl_transcript_destroy(zkdl_transcript* t) {
 }
 
 extern "C" int zkdl_transcript_absorb(zkdl_transcript* t, const char* label, const void* bytes, size_t n) {
-    if (!t || !label || (!bytes && n) || n > 0x7fffffffu) return ZKDL_EINVAL;
+    if (!t || !label || (!bytes && n)) return ZKDL_EINVAL;
     size_t ll = strlen(label);
     if (ll > ts::MAX_LABEL) return ZKDL_EINVAL;
-    std::vector<uint8_t> buf(ts::scratch_bytes((uint32_t)n));
-    ts::absorb(t->state, label, (uint32_t)ll, (const uint8_t*)bytes, (uint32_t)n, buf.data());
+    ts::absorb(t->s, label, (uint32_t)ll, (const uint8_t*)bytes, (uint64_t)n);
     return ZKDL_OK;
 }
 
 extern "C" int zkdl_transcript_challenge(zkdl_transcript* t, zkdl_fr* host_out) {
     if (!t || !host_out) return ZKDL_EINVAL;
-    ts::challenge(t->state, host_out->le);
+    ts::challenge(t->s, host_out->le);
     return ZKDL_OK;
 }
 
 extern "C" int zkdl_transcript_digest(const zkdl_transcript* t, uint8_t host_out[32]) {
     if (!t || !host_out) return ZKDL_EINVAL;
-    memcpy(host_out, t->state, 32);
+    ts::digest(t->s, host_out);
     return ZKDL_OK;
 }
 
@@ -474,18 +468,17 @@ struct AbsorbWordsArg {
 };
 
 __global__ void k_absorb_words(DevState* st, AbsorbWordsArg a) {
-    __shared__ uint8_t lds[256];
     if (threadIdx.x != 0) return;
     uint8_t data[32];
     for (uint32_t i = 0; i < a.n; ++i)
         for (int b = 0; b < 4; ++b) data[4 * i + b] = (uint8_t)(a.words[i] >> (8 * b));
-    uint8_t state[32];
-    uint32_t w[8];
-    for (int i = 0; i < 8; ++i) w[i] = st->ts_state[i];
-    sha::words_to_bytes(w, state);
-    ts::absorb(state, a.label, a.label_len, data, 4 * a.n, lds);
-    sha::bytes_to_words(state, w);
-    for (int i = 0; i < 8; ++i) st->ts_state[i] = w[i];
+    ts::State s;
+    for (int i = 0; i < 8; ++i) s.h[i] = st->ts_state[i];
+    s.nblk = ((uint64_t)st->ts_nblk[1] << 32) | st->ts_nblk[0];
+    ts::absorb(s, a.label, a.label_len, data, 4 * a.n);
+    for (int i = 0; i < 8; ++i) st->ts_state[i] = s.h[i];
+    st->ts_nblk[0] = (uint32_t)s.nblk;
+    st->ts_nblk[1] = (uint32_t)(s.nblk >> 32);
 }
 
 // header of a protocol: a label and up to 8 little-endian u32 words, absorbed in stream order
@@ -508,7 +501,12 @@ static int call_begin(zkdl_ctx* ctx, zkdl_transcript* tr) {
     g_patches.clear();
     // state + cleared error word
     memset(ctx->host_stage, 0, 64);
-    sha::bytes_to_words(tr->state, (uint32_t*)ctx->host_stage);
+    {
+        DevState* h = (DevState*)ctx->host_stage;
+        for (int i = 0; i < 8; ++i) h->ts_state[i] = tr->s.h[i];
+        h->ts_nblk[0] = (uint32_t)tr->s.nblk;
+        h->ts_nblk[1] = (uint32_t)(tr->s.nblk >> 32);
+    }
     ZK_HIP(ctx, hipMemcpyAsync(ctx->dev, ctx->host_stage, 64, hipMemcpyHostToDevice, ctx->stream));
     return ZKDL_OK;
 }
@@ -530,7 +528,8 @@ static int call_end(zkdl_ctx* ctx, zkdl_transcript* tr, uint8_t* proof, size_t* 
     if (ctx->prof_on) prof_collect(ctx);
     const DevState* h = (const DevState*)hs;
     if (h->err & 1u) return ZKDL_ERANGE;
-    sha::words_to_bytes(h->ts_state, tr->state);
+    for (int i = 0; i < 8; ++i) tr->s.h[i] = h->ts_state[i];
+    tr->s.nblk = ((uint64_t)h->ts_nblk[1] << 32) | h->ts_nblk[0];
     int rc = ZKDL_OK;
     if (proof_len) {
         if (!proof || *proof_len < ctx->proof_len) {

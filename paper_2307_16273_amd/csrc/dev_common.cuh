@@ -40,13 +40,63 @@ __device__ __forceinline__ Fr block_sum(Fr x, uint32_t* red) {
     return x;
 }
 
+// Sums N lazy values per thread (normal limbs, each below 2.41 r) over a block of at most
+// 8 waves; thread j < N returns the fully reduced sum of value j, other threads zero.
+// Limbs are added without carries: three shuffle levels take them from below 2^29 to below
+// 2^32, a carry pass follows, three more levels, then a reducing pass (the wave's sum is
+// below 64 * 2.41 r < 2^263); at most 8 such wave sums are added before the final reduction.
+// red: BLOCK_SUM_LAZY_WORDS words of LDS.
+constexpr int BLOCK_SUM_LAZY_WORDS = 8 * ZK_MAX_EVALS * 9;
+template <int N>
+__device__ __forceinline__ Fr block_sum_lazy(const F9 (&x)[N], uint32_t* red) {
+    static_assert(N <= ZK_MAX_EVALS, "red is sized for ZK_MAX_EVALS values");
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n_waves = (blockDim.x + 63) >> 6;
+    F9 s[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) s[j] = x[j];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+#pragma unroll
+            for (int l = 0; l < 9; ++l) s[j].v[l] += __shfl_down(s[j].v[l], off, 64);
+        if (off == 8) {
+#pragma unroll
+            for (int j = 0; j < N; ++j) s[j] = f9_norm(s[j]);
+        }
+    }
+    __syncthreads();   // red may still be read from a previous call
+    if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const F9 r = f9_norm_reduce(s[j]);
+#pragma unroll
+            for (int l = 0; l < 9; ++l) red[(wave * N + j) * 9 + l] = r.v[l];
+        }
+    }
+    __syncthreads();
+    Fr out = fr_zero();
+    if (tid < N) {
+        F9 t = f9_zero();
+        for (int w = 0; w < n_waves; ++w)
+#pragma unroll
+            for (int l = 0; l < 9; ++l) t.v[l] += red[(w * N + tid) * 9 + l];
+        out = f9_to_fr(t);
+    }
+    return out;
+}
+
 constexpr int TS_MAX_ABSORB = 8;     // field elements per device-side absorb
 constexpr int TS_MAX_DRAW = 64;      // challenges per block_challenges chunk
+constexpr int TS_MAX_FRAME_BLOCKS = (10 + 32 * TS_MAX_ABSORB + 63) / 64;
 
 // LDS working set of the transcript steps
 struct TsShared {
-    uint32_t state[8];                       // transcript state, big-endian words
-    uint32_t msg[96];                        // padded message, big-endian words (<= 6 blocks)
+    uint32_t state[8];                       // chaining value after the last block of the stream
+    uint64_t nblk;                           // blocks in the stream
+    uint32_t msg[16 * TS_MAX_FRAME_BLOCKS];  // frame being absorbed, big-endian words
+    uint32_t wk[TS_MAX_FRAME_BLOCKS + 3][64];// schedules: frame blocks, then a draw's three blocks
     uint32_t canon[TS_MAX_ABSORB][8];        // canonical little-endian limbs being absorbed
     uint32_t dig[2 * TS_MAX_DRAW + 1][8];    // digests of a challenge draw
     Fr tmp[TS_MAX_ABSORB];
@@ -55,54 +105,72 @@ struct TsShared {
 
 __device__ __forceinline__ void block_ts_load(TsShared& S, const DevState* st) {
     if (threadIdx.x < 8) S.state[threadIdx.x] = st->ts_state[threadIdx.x];
+    if (threadIdx.x == 8) S.nblk = ((uint64_t)st->ts_nblk[1] << 32) | st->ts_nblk[0];
     __syncthreads();
 }
 
 __device__ __forceinline__ void block_ts_store(const TsShared& S, DevState* st) {
     __syncthreads();
     if (threadIdx.x < 8) st->ts_state[threadIdx.x] = S.state[threadIdx.x];
+    if (threadIdx.x == 8) {
+        st->ts_nblk[0] = (uint32_t)S.nblk;
+        st->ts_nblk[1] = (uint32_t)(S.nblk >> 32);
+    }
 }
 
-// state <- SHA256(state || 0x01 || label || u64le(32 count) || canon[0..count))
-// for a one-character label; canon must be complete (a barrier is taken first).
-__device__ inline void block_absorb1(TsShared& S, char label, int count) {
+// blocks of the frame of `count` field elements under a one-character label
+__device__ __forceinline__ uint32_t ts_frame_blocks(int count) { return (10u + 32u * (uint32_t)count + 63u) / 64u; }
+
+// stream <- stream || pad64(0x01 || label || u64le(32 count) || canon[0..count)) for a
+// one-character label; canon must be complete (a barrier is taken first).  Lane j of
+// wave 0 prepares the schedule of frame block j, then lane 0 runs the rounds block after
+// block.  With draw1 the three blocks of a single-challenge draw that follows this absorb
+// (halves 0xF0, 0xF1 at index 0, and the 0xF2 block) get their schedules in the same step,
+// in wk[nb .. nb + 3), nb = ts_frame_blocks(count): they depend on the block count only.
+__device__ inline void block_absorb1(TsShared& S, char label, int count, bool draw1) {
     __syncthreads();
-    const uint32_t total = 42u + 32u * (uint32_t)count;
-    const uint32_t padded = ((total + 9 + 63) / 64) * 64;
+    const uint32_t total = 10u + 32u * (uint32_t)count;
+    const uint32_t nb = ts_frame_blocks(count);
     const uint32_t data_len = 32u * (uint32_t)count;
     // every thread builds whole message words, byte by byte
-    for (uint32_t j = threadIdx.x; j < padded / 4; j += blockDim.x) {
+    for (uint32_t j = threadIdx.x; j < 16 * nb; j += blockDim.x) {
         uint32_t word = 0;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const uint32_t p = 4 * j + b;
             uint32_t byte;
-            if (p < 32) byte = (S.state[p >> 2] >> (24 - 8 * (p & 3))) & 0xffu;
-            else if (p == 32) byte = 1;
-            else if (p == 33) byte = (uint8_t)label;
-            else if (p < 42) byte = (p - 34 < 4) ? ((data_len >> (8 * (p - 34))) & 0xffu) : 0u;
+            if (p == 0) byte = 1;
+            else if (p == 1) byte = (uint8_t)label;
+            else if (p < 10) byte = (p - 2 < 4) ? ((data_len >> (8 * (p - 2))) & 0xffu) : 0u;
             else if (p < total) {
-                const uint32_t q = p - 42;
+                const uint32_t q = p - 10;
                 byte = (S.canon[q >> 5][(q & 31) >> 2] >> (8 * (q & 3))) & 0xffu;
-            } else if (p == total) byte = 0x80u;
-            else if (p >= padded - 4) byte = ((total * 8) >> (8 * (padded - 1 - p))) & 0xffu;
-            else byte = 0;
+            } else byte = 0;
             word = (word << 8) | byte;
         }
         S.msg[j] = word;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        sha::Words8 h = sha::iv_words();
-        const uint32_t nblocks = padded / 64;
-        for (uint32_t blk = 0; blk < nblocks; ++blk) {
-            sha::Words16 w;
+    const uint64_t nblk_after = S.nblk + nb;
+    if (threadIdx.x < nb + (draw1 ? 3u : 0u)) {
+        sha::Words16 w;
+        if (threadIdx.x < nb) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) w.v[i] = S.msg[16 * blk + i];
-            h = sha::compress_ni(h, w);
+            for (int i = 0; i < 16; ++i) w.v[i] = S.msg[16 * threadIdx.x + i];
+        } else {
+            w = sha::draw_block_words(0xF0u + (threadIdx.x - nb), 0u, nblk_after);
         }
+        sha::schedule_wk_lds(w, S.wk[threadIdx.x]);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        sha::Words8 h;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
+        for (uint32_t blk = 0; blk < nb; ++blk) h = sha::rounds_lds(h, S.wk[blk]);
 #pragma unroll
         for (int i = 0; i < 8; ++i) S.state[i] = h.v[i];
+        S.nblk = nblk_after;
     }
     __syncthreads();
 }
@@ -119,10 +187,10 @@ __device__ inline void block_absorb_frs(TsShared& S, char label, const Fr* vals,
             if (proof_dst) proof_dst[8 * threadIdx.x + l] = plain.v[l];
         }
     }
-    block_absorb1(S, label, count);
+    block_absorb1(S, label, count, false);
 }
 
-// draws `count` challenges into st->chal[base..), st->chal_le; one state update.
+// draws `count` challenges into st->chal[base..), st->chal_le; one stream extension.
 // The first one is also left in S.v.
 __device__ inline void block_challenges(TsShared& S, DevState* st, int base, int count) {
     if (count <= 0) return;
@@ -132,12 +200,13 @@ __device__ inline void block_challenges(TsShared& S, DevState* st, int base, int
         const bool last = c0 + n >= count;
         const int jobs = 2 * n + (last ? 1 : 0);
         for (int t = threadIdx.x; t < jobs; t += blockDim.x) {
-            uint32_t stw[8];
+            sha::Words8 h;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) stw[i] = S.state[i];
+            for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
             const bool elem = t < 2 * n;
-            sha::Words8 out = sha::digest_state_suffix_ni(stw, elem ? (uint32_t)(t & 1) : 2u, elem,
-                                                          elem ? (uint32_t)(c0 + (t >> 1)) : 0u);
+            const sha::Words16 w = sha::draw_block_words(elem ? 0xF0u + (uint32_t)(t & 1) : 0xF2u,
+                                                         elem ? (uint32_t)(c0 + (t >> 1)) : 0u, S.nblk);
+            const sha::Words8 out = sha::compress_ni(h, w);
 #pragma unroll
             for (int i = 0; i < 8; ++i) S.dig[t][i] = out.v[i];
         }
@@ -168,7 +237,10 @@ __device__ inline void block_challenges(TsShared& S, DevState* st, int base, int
             for (int l = 0; l < 8; ++l) le[l] = plain.v[l];
         }
         __syncthreads();
-        if (last && threadIdx.x < 8) S.state[threadIdx.x] = S.dig[2 * n][threadIdx.x];
+        if (last) {
+            if (threadIdx.x < 8) S.state[threadIdx.x] = S.dig[2 * n][threadIdx.x];
+            if (threadIdx.x == 8) S.nblk += 1;
+        }
         __syncthreads();
     }
 }
@@ -187,12 +259,14 @@ __device__ inline Fr block_finalise_round(TsShared& S, DevState* st, const Fr* g
     const int tid = threadIdx.x;
     uint32_t* proof_dst = (uint32_t*)(st->proof + proof_off);
     __syncthreads();
-    // canonical forms (wave 0) | Lagrange coefficients (wave 1)
+    // canonical forms (wave 0) | Lagrange coefficients (wave 1).  The transcript takes
+    // g(0), g(2), .., g(npts-1): g(1) is fixed by the claim the transcript already determines.
     if (tid < npts) {
         Fr plain = fr_from_mont_ni(g[tid]);
+        const int slot = tid == 0 ? 0 : tid - 1;
 #pragma unroll
         for (int l = 0; l < 8; ++l) {
-            S.canon[tid][l] = plain.v[l];
+            if (tid != 1) S.canon[slot][l] = plain.v[l];
             proof_dst[8 * tid + l] = plain.v[l];
         }
     } else if (tid >= 64 && tid < 64 + npts) {
@@ -208,26 +282,24 @@ __device__ inline Fr block_finalise_round(TsShared& S, DevState* st, const Fr* g
         }
         S.tmp[k] = c;
     }
-    block_absorb1(S, 'g', npts);
-    // challenge hashes: lanes 0, 1 (element), 2 (next state)
+    block_absorb1(S, 'g', npts - 1, true);
+    // challenge hashes on the schedules prepared during the absorb: lanes 0, 1 (the two
+    // halves of the element), 2 (the block that extends the stream)
     if (tid < 3) {
-        uint32_t stw[8];
+        sha::Words8 h;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) stw[i] = S.state[i];
-        const sha::Words8 ow = sha::digest_state_suffix_ni(stw, tid < 2 ? (uint32_t)tid : 2u, tid < 2, 0u);
-        uint32_t out[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = ow.v[i];
+        for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
+        const sha::Words8 ow = sha::rounds_lds(h, S.wk[ts_frame_blocks(npts - 1) + tid]);
         if (tid < 2) {
             Fr x;
 #pragma unroll
-            for (int l = 0; l < 8; ++l) x.v[l] = sha::bswap32(out[l]);
+            for (int l = 0; l < 8; ++l) x.v[l] = sha::bswap32(ow.v[l]);
             Fr m = fr_mul_ni(fr_const(tid ? frc::W3 : frc::R2), x);
 #pragma unroll
             for (int l = 0; l < 8; ++l) S.dig[tid][l] = m.v[l];
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) S.dig[2][i] = out[i];
+            for (int i = 0; i < 8; ++i) S.dig[2][i] = ow.v[i];
         }
     }
     __syncthreads();
@@ -239,6 +311,7 @@ __device__ inline Fr block_finalise_round(TsShared& S, DevState* st, const Fr* g
     }
     const Fr v = fr_add(lo, hi);   // every thread
     if (tid < 8) S.state[tid] = S.dig[2][tid];
+    if (tid == 8) S.nblk += 1;
     if (tid == 0) st->chal[chal_idx] = v;
     // first level of the Lagrange sum (wave 0, one product per lane) | canonical v (wave 1)
     const Fr one = fr_one();

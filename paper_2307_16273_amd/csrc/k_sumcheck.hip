@@ -84,7 +84,7 @@ __device__ __forceinline__ void sc_pair(const RoundArgs& a, uint64_t b, uint64_t
 
 template <int K, int MODE>
 __global__ __launch_bounds__(ZK_BLOCK) void k_sc_round(RoundArgs a) {
-    __shared__ uint32_t red[64];
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     F9 acc[K + 1];
 #pragma unroll
     for (int x = 0; x <= K; ++x) acc[x] = f9_zero();
@@ -101,10 +101,15 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_round(RoundArgs a) {
             for (int x = 0; x <= K; ++x) acc[x] = f9_norm_reduce(acc[x]);
         }
     }
+    // fused rounds leave g(1) out: K sums instead of K + 1
+    constexpr int NS = MODE != 0 ? K : K + 1;
+    F9 need[NS];
 #pragma unroll
-    for (int x = 0; x <= K; ++x) {
-        Fr s = block_sum(f9_to_fr(acc[x]), red);
-        if (threadIdx.x == 0) a.part[(uint64_t)blockIdx.x * (K + 1) + x] = s;
+    for (int j = 0; j < NS; ++j) need[j] = f9_norm_reduce(acc[(MODE != 0 && j >= 1) ? j + 1 : j]);
+    const Fr s = block_sum_lazy<NS>(need, red);
+    if (threadIdx.x < NS) {
+        const int x = (MODE != 0 && threadIdx.x >= 1) ? threadIdx.x + 1 : threadIdx.x;
+        a.part[(uint64_t)blockIdx.x * (K + 1) + x] = s;
     }
 }
 
@@ -219,7 +224,7 @@ struct ScTailArgs {
 // as k_sc_round<K, 2>, round after round with barriers in between, then the final fold.
 template <int K>
 __global__ __launch_bounds__(ZK_BLOCK) void k_sc_tail(ScTailArgs a) {
-    __shared__ uint32_t red[64];
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ TsShared S;
     __shared__ Fr g[ZK_MAX_EVALS + 1];
     DevState* st = a.st;
@@ -239,13 +244,14 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_tail(ScTailArgs a) {
                 for (int x = 0; x <= K; ++x) acc[x] = f9_norm_reduce(acc[x]);
             }
         }
+        {
+            F9 need[K];
 #pragma unroll
-        for (int x = 0; x <= K; ++x) {
-            if (x == 1) continue;
-            Fr s = block_sum(f9_to_fr(acc[x]), red);
-            if (threadIdx.x == 0) g[x] = s;
+            for (int j = 0; j < K; ++j) need[j] = f9_norm_reduce(acc[j >= 1 ? j + 1 : j]);
+            const Fr s = block_sum_lazy<K>(need, red);
+            if (threadIdx.x < K) g[threadIdx.x >= 1 ? threadIdx.x + 1 : 0] = s;
+            if (threadIdx.x == 0) g[1] = fr_sub(st->claim, s);
         }
-        if (threadIdx.x == 0) g[1] = fr_sub(st->claim, g[0]);
         __syncthreads();
         Fr vr = block_finalise_round(S, st, g, K + 1, a.rounds_off + (uint32_t)t * (K + 1) * 32,
                                      a.first_chal + 1 + t);

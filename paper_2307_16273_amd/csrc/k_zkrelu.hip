@@ -206,7 +206,7 @@ __device__ __forceinline__ void line3(const F9& lo, const F9& hi, F9 e[3]) {
 // at x = 0, 2, 3 (x = 1 comes from the claim); beta_I is folded along for the binarity kernels.
 template <bool FOLD>
 __global__ __launch_bounds__(ZK_BLOCK) void k_zk_lin(LinArgs a) {
-    __shared__ uint32_t red[64];
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     F9 acc[3];
 #pragma unroll
     for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
@@ -250,15 +250,11 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_lin(LinArgs a) {
             for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
         }
     }
-    Fr s0 = block_sum(f9_to_fr(acc[0]), red);
-    Fr s2 = block_sum(f9_to_fr(acc[1]), red);
-    Fr s3 = block_sum(f9_to_fr(acc[2]), red);
-    if (threadIdx.x == 0) {
+    {   // thread j holds the sum for x = 0, 2, 3; g(1) is derived from the claim
+        const Fr s = block_sum_lazy<3>(acc, red);
         Fr* pp = a.part + (uint64_t)blockIdx.x * 4;
-        pp[0] = s0;
-        pp[1] = fr_zero();
-        pp[2] = s2;
-        pp[3] = s3;
+        if (threadIdx.x < 3) pp[threadIdx.x ? threadIdx.x + 1 : 0] = s;
+        else if (threadIdx.x == 3) pp[1] = fr_zero();
     }
 }
 
@@ -387,7 +383,7 @@ __device__ __forceinline__ void beta_line(const F9Tab& bI, uint64_t b, uint64_t 
 // Round 1 by look-up.  m = D/4 quadruples (i'', i''+m | i''+2m, i''+3m) = (x0, x1) in
 // {(0,0), (0,1), (1,0), (1,1)}.  Writes partial sums for x = 0, 2, 3 (x = 1 comes from the claim).
 __global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin1(BinArgs a) {
-    __shared__ uint32_t red[64];
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ F9 sbj[64];
     __shared__ F9 qx[2][3][16];   // [slice][x in {0,2,3}][combination]; slice 1 carries r'
     const int tid = threadIdx.x;
@@ -444,15 +440,11 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin1(BinArgs a) {
         for (int x = 0; x < 3; ++x)
             tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_norm_reduce(acc[x]))));
     }
-    Fr s0 = block_sum(f9_to_fr(tot[0]), red);
-    Fr s2 = block_sum(f9_to_fr(tot[1]), red);
-    Fr s3 = block_sum(f9_to_fr(tot[2]), red);
-    if (tid == 0) {
+    {
+        const Fr s = block_sum_lazy<3>(tot, red);
         Fr* p = a.part + (uint64_t)blockIdx.x * 4;
-        p[0] = s0;
-        p[1] = fr_zero();
-        p[2] = s2;
-        p[3] = s3;
+        if (tid < 3) p[tid ? tid + 1 : 0] = s;
+        else if (tid == 3) p[1] = fr_zero();
     }
 }
 
@@ -491,7 +483,7 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat2(BinArgs a) {
 // of beta_J(j) q(x) (slice 1 with r' beta_J), then times beta_I(x, i').
 template <bool FOLD>
 __global__ __launch_bounds__(ZK_BLOCK) void k_zk_binl(BinArgs a) {
-    __shared__ uint32_t red[64];
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ F9 sbj[2][64];
     const int tid = threadIdx.x;
     if (tid < 128) {
@@ -556,15 +548,11 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_binl(BinArgs a) {
             tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_norm_reduce(acc[x]))));
     }
     const uint64_t blk = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
-    Fr s0 = block_sum(f9_to_fr(tot[0]), red);
-    Fr s2 = block_sum(f9_to_fr(tot[1]), red);
-    Fr s3 = block_sum(f9_to_fr(tot[2]), red);
-    if (tid == 0) {
+    {
+        const Fr s = block_sum_lazy<3>(tot, red);
         Fr* p = a.part + blk * 4;
-        p[0] = s0;
-        p[1] = fr_zero();
-        p[2] = s2;
-        p[3] = s3;
+        if (tid < 3) p[tid ? tid + 1 : 0] = s;
+        else if (tid == 3) p[1] = fr_zero();
     }
 }
 

@@ -2,13 +2,19 @@
 // host code and from a single GPU thread.
 //
 // The paper's verifier sends a uniform field element after each round
-// polynomial (App. B); the transcript replaces that message by a hash:
-//   state_0          = SHA256("zkdl-mi355x/v1" || u64le(seed))
-//   absorb(label, m) : state <- SHA256(state || u8(|label|) || label || u64le(|m|) || m)
-//   challenges(n)    : for i < n: d0 = SHA256(state || 0x00 || u32le(i)),
-//                      d1 = SHA256(state || 0x01 || u32le(i)), c_i = int_le(d0 || d1) mod r;
-//                      then state <- SHA256(state || 0x02).  challenge() = challenges(1)[0].
-//                      The n elements of one draw are independent hashes: one per lane.
+// polynomial (App. B); the transcript replaces that message by a hash.  The
+// transcript is one byte stream, always a whole number of 64-byte blocks:
+//   stream_0         = "zkdl-mi355x/v2" zero-padded to 56 bytes || u64le(seed)
+//   absorb(label, m) : stream <- stream || pad64(u8(|label|) || label || u64le(|m|) || m)
+//   challenges(n)    : for i < n: d0 = SHA256(stream || 0xF0 || u32le(i)),
+//                      d1 = SHA256(stream || 0xF1 || u32le(i)), c_i = int_le(d0 || d1) mod r;
+//                      then stream <- stream || 0xF2 || 63 zero bytes.  challenge() = challenges(1)[0].
+//   digest()         = SHA256(stream)
+// The state is the SHA-256 chaining value after the last block and the block count:
+// an absorb is one compression per 64 message bytes, every hash of a draw is one
+// compression from the chaining value (its block: tag, index, padding, bit length), and
+// the message schedules of all of these do not depend on the chaining value, so they
+// are computed beforehand, in other lanes than the one that runs the rounds.
 #pragma once
 #include <stdint.h>
 #include <hip/hip_runtime.h>
@@ -132,77 +138,71 @@ __device__ inline Words8 iv_words() {
     return h;
 }
 
-// SHA256(state || suffix [|| u32le(idx)]) through the compact compression
-__device__ inline Words8 digest_state_suffix_ni(const uint32_t st[8], uint32_t suffix, bool with_idx,
-                                                uint32_t idx) {
-    Words16 w;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) w.v[i] = st[i];
-    if (with_idx) {
-        w.v[8] = (suffix << 24) | ((idx & 0xffu) << 16) | (((idx >> 8) & 0xffu) << 8) | ((idx >> 16) & 0xffu);
-        w.v[9] = ((idx >> 24) << 24) | 0x00800000u;
-    } else {
-        w.v[8] = (suffix << 24) | 0x00800000u;
-        w.v[9] = 0;
-    }
-#pragma unroll
-    for (int i = 10; i < 15; ++i) w.v[i] = 0;
-    w.v[15] = with_idx ? 37 * 8 : 33 * 8;
-    return compress_ni(iv_words(), w);
-}
-#endif
-
-// digest of msg[0..len).  The buffer must have room for the padding: its
-// capacity must be at least ((len + 9 + 63) / 64) * 64 bytes; it is overwritten.
-SHA_HD void digest_inplace(uint8_t* msg, uint32_t len, uint8_t out[32]) {
-    uint32_t total = ((len + 9 + 63) / 64) * 64;
-    msg[len] = 0x80;
-    for (uint32_t i = len + 1; i < total - 8; ++i) msg[i] = 0;
-    uint64_t bits = (uint64_t)len * 8;
-    for (int i = 0; i < 8; ++i) msg[total - 1 - i] = (uint8_t)(bits >> (8 * i));
-    uint32_t h[8] = {0x6a09e667, 0xbb67ae85, 0x3c6ef372, 0xa54ff53a,
-                     0x510e527f, 0x9b05688c, 0x1f83d9ab, 0x5be0cd19};
-    for (uint32_t off = 0; off < total; off += 64) {
-        uint32_t w[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const uint8_t* p = msg + off + 4 * i;
-            w[i] = ((uint32_t)p[0] << 24) | ((uint32_t)p[1] << 16) | ((uint32_t)p[2] << 8) | p[3];
-        }
-        compress(h, w);
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        out[4 * i] = (uint8_t)(h[i] >> 24);
-        out[4 * i + 1] = (uint8_t)(h[i] >> 16);
-        out[4 * i + 2] = (uint8_t)(h[i] >> 8);
-        out[4 * i + 3] = (uint8_t)h[i];
-    }
-}
-
-// SHA256(state || suffix [|| u32le(idx)]) from registers only; state and result as
-// the eight big-endian words of the digest
-SHA_HD void digest_state_suffix_w(const uint32_t st[8], uint32_t suffix, bool with_idx, uint32_t idx,
-                                  uint32_t out[8]) {
+// wk[0..64) = W[t] + K[t] of one block, written to LDS; compact (one 16-step loop body)
+static __device__ __noinline__ void schedule_wk_lds(Words16 win, uint32_t* wk) {
     uint32_t w[16];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) w[i] = st[i];
-    if (with_idx) {
-        w[8] = (suffix << 24) | ((idx & 0xffu) << 16) | (((idx >> 8) & 0xffu) << 8) | ((idx >> 16) & 0xffu);
-        w[9] = ((idx >> 24) << 24) | 0x00800000u;
-    } else {
-        w[8] = (suffix << 24) | 0x00800000u;
-        w[9] = 0;
+    for (int i = 0; i < 16; ++i) {
+        w[i] = win.v[i];
+        wk[i] = w[i] + K_TABLE[i];
     }
+#pragma unroll 1
+    for (int r = 1; r < 4; ++r) {
 #pragma unroll
-    for (int i = 10; i < 15; ++i) w[i] = 0;
-    w[15] = with_idx ? 37 * 8 : 33 * 8;
-    uint32_t h[8] = {0x6a09e667, 0xbb67ae85, 0x3c6ef372, 0xa54ff53a,
-                     0x510e527f, 0x9b05688c, 0x1f83d9ab, 0x5be0cd19};
-    compress(h, w);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) out[i] = h[i];
+        for (int i = 0; i < 16; ++i) {
+            uint32_t w15 = w[(i + 1) & 15], w2 = w[(i + 14) & 15];
+            uint32_t s0 = rotr(w15, 7) ^ rotr(w15, 18) ^ (w15 >> 3);
+            uint32_t s1 = rotr(w2, 17) ^ rotr(w2, 19) ^ (w2 >> 10);
+            w[i] = w[i] + s0 + w[(i + 9) & 15] + s1;
+            wk[16 * r + i] = w[i] + K_TABLE[16 * r + i];
+        }
+    }
 }
+
+// the 64 rounds on a schedule prepared in LDS; compact (one 8-round loop body)
+static __device__ __noinline__ Words8 rounds_lds(Words8 hin, const uint32_t* wk) {
+    uint32_t a = hin.v[0], b = hin.v[1], c = hin.v[2], d = hin.v[3], e = hin.v[4], f = hin.v[5],
+             g = hin.v[6], hh = hin.v[7];
+#pragma unroll 1
+    for (int r = 0; r < 8; ++r) {
+        uint32_t x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = wk[8 * r + i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint32_t S1 = rotr(e, 6) ^ rotr(e, 11) ^ rotr(e, 25);
+            uint32_t ch = (e & f) | (~e & g);
+            uint32_t t1 = hh + S1 + ch + x[i];
+            uint32_t S0 = rotr(a, 2) ^ rotr(a, 13) ^ rotr(a, 22);
+            uint32_t ab = a ^ b;
+            uint32_t mj = (ab & c) | (~ab & b);
+            hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + S0 + mj;
+        }
+    }
+    Words8 o;
+    o.v[0] = hin.v[0] + a; o.v[1] = hin.v[1] + b; o.v[2] = hin.v[2] + c; o.v[3] = hin.v[3] + d;
+    o.v[4] = hin.v[4] + e; o.v[5] = hin.v[5] + f; o.v[6] = hin.v[6] + g; o.v[7] = hin.v[7] + hh;
+    return o;
+}
+
+// The block that closes SHA256(stream || tag || u32le(idx)) for a stream of nblk whole
+// blocks (tag 0xF0 / 0xF1), or the block 0xF2 || zeros appended after a draw (tag 0xF2).
+__device__ inline Words16 draw_block_words(uint32_t tag, uint32_t idx, uint64_t nblk) {
+    Words16 w;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) w.v[i] = 0;
+    if (tag == 0xF2u) {
+        w.v[0] = 0xF2000000u;
+    } else {
+        w.v[0] = (tag << 24) | ((idx & 0xffu) << 16) | (((idx >> 8) & 0xffu) << 8) | ((idx >> 16) & 0xffu);
+        w.v[1] = ((idx >> 24) << 24) | 0x00800000u;
+        const uint64_t bits = nblk * 512u + 40u;
+        w.v[14] = (uint32_t)(bits >> 32);
+        w.v[15] = (uint32_t)bits;
+    }
+    return w;
+}
+#endif
 
 SHA_HD uint32_t bswap32(uint32_t x) {
     return (x >> 24) | ((x >> 8) & 0xff00u) | ((x << 8) & 0xff0000u) | (x << 24);
@@ -229,56 +229,91 @@ SHA_HD void words_to_bytes(const uint32_t w[8], uint8_t b[32]) {
 namespace ts {
 
 constexpr uint32_t MAX_LABEL = 32;
-// scratch needed by absorb() for `n` data bytes
-SHA_HD uint32_t scratch_bytes(uint32_t n) { return ((32 + 1 + MAX_LABEL + 8 + n + 9 + 63) / 64) * 64; }
 
-// state <- SHA256(state || u8(label_len) || label || u64le(n) || data); `buf` is
-// scratch of at least scratch_bytes(n) bytes (LDS on the device)
-SHA_HD void absorb(uint8_t state[32], const char* label, uint32_t label_len, const uint8_t* data,
-                   uint32_t n, uint8_t* buf) {
-    uint32_t p = 0;
-    for (int i = 0; i < 32; ++i) buf[p++] = state[i];
-    buf[p++] = (uint8_t)label_len;
-    for (uint32_t i = 0; i < label_len; ++i) buf[p++] = (uint8_t)label[i];
-    uint64_t n64 = n;
-    for (int i = 0; i < 8; ++i) buf[p++] = (uint8_t)(n64 >> (8 * i));
-    for (uint32_t i = 0; i < n; ++i) buf[p++] = data[i];
-    sha::digest_inplace(buf, p, state);
+// chaining value after the last whole block of the stream, and the number of blocks
+struct State {
+    uint32_t h[8];
+    uint64_t nblk;
+};
+
+SHA_HD void push_block(State& s, const uint8_t blk[64]) {
+    uint32_t w[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint8_t* p = blk + 4 * i;
+        w[i] = ((uint32_t)p[0] << 24) | ((uint32_t)p[1] << 16) | ((uint32_t)p[2] << 8) | p[3];
+    }
+    sha::compress(s.h, w);
+    s.nblk += 1;
 }
 
-// element i of a draw from the state given as big-endian words (Montgomery form)
-SHA_HD Fr challenge_elem_w(const uint32_t st[8], uint32_t idx) {
-    uint32_t d0[8], d1[8];
-    sha::digest_state_suffix_w(st, 0x00, true, idx, d0);
-    sha::digest_state_suffix_w(st, 0x01, true, idx, d1);
+SHA_HD void init(State& s, uint64_t seed) {
+    const uint32_t iv[8] = {0x6a09e667, 0xbb67ae85, 0x3c6ef372, 0xa54ff53a,
+                            0x510e527f, 0x9b05688c, 0x1f83d9ab, 0x5be0cd19};
+    for (int i = 0; i < 8; ++i) s.h[i] = iv[i];
+    s.nblk = 0;
+    const char dom[] = "zkdl-mi355x/v2";
+    uint8_t blk[64];
+    for (int i = 0; i < 64; ++i) blk[i] = 0;
+    for (int i = 0; i < (int)sizeof(dom) - 1; ++i) blk[i] = (uint8_t)dom[i];
+    for (int i = 0; i < 8; ++i) blk[56 + i] = (uint8_t)(seed >> (8 * i));
+    push_block(s, blk);
+}
+
+// stream <- stream || pad64(u8(label_len) || label || u64le(n) || data), block by block
+SHA_HD void absorb(State& s, const char* label, uint32_t label_len, const uint8_t* data, uint64_t n) {
+    uint8_t blk[64];
+    uint32_t p = 0;
+    blk[p++] = (uint8_t)label_len;
+    for (uint32_t i = 0; i < label_len; ++i) blk[p++] = (uint8_t)label[i];   // label_len <= 32
+    for (int i = 0; i < 8; ++i) blk[p++] = (uint8_t)(n >> (8 * i));
+    for (uint64_t i = 0; i < n; ++i) {
+        if (p == 64) {
+            push_block(s, blk);
+            p = 0;
+        }
+        blk[p++] = data[i];
+    }
+    while (p < 64) blk[p++] = 0;
+    push_block(s, blk);
+}
+
+// SHA256(stream || tail), tail of at most 55 bytes, as big-endian words
+SHA_HD void tail_digest_w(const State& s, const uint8_t* tail, uint32_t tail_len, uint32_t out[8]) {
+    uint8_t blk[64];
+    for (int i = 0; i < 64; ++i) blk[i] = 0;
+    for (uint32_t i = 0; i < tail_len; ++i) blk[i] = tail[i];
+    blk[tail_len] = 0x80;
+    const uint64_t bits = (s.nblk * 64 + tail_len) * 8;
+    for (int i = 0; i < 8; ++i) blk[63 - i] = (uint8_t)(bits >> (8 * i));
+    State f = s;
+    push_block(f, blk);
+    for (int i = 0; i < 8; ++i) out[i] = f.h[i];
+}
+
+// element idx of a draw (Montgomery form)
+SHA_HD Fr challenge_elem(const State& s, uint32_t idx) {
+    uint32_t d[2][8];
+    for (uint32_t j = 0; j < 2; ++j) {
+        const uint8_t tail[5] = {(uint8_t)(0xF0 + j), (uint8_t)idx, (uint8_t)(idx >> 8), (uint8_t)(idx >> 16),
+                                 (uint8_t)(idx >> 24)};
+        tail_digest_w(s, tail, 5, d[j]);
+    }
     Fr lo, hi;
 #pragma unroll
     for (int l = 0; l < 8; ++l) {
-        lo.v[l] = sha::bswap32(d0[l]);   // little-endian limbs of the digest bytes
-        hi.v[l] = sha::bswap32(d1[l]);
+        lo.v[l] = sha::bswap32(d[0][l]);   // little-endian limbs of the digest bytes
+        hi.v[l] = sha::bswap32(d[1][l]);
     }
     return fr_from_wide(lo, hi);
 }
 
-// draw one challenge; returns it in Montgomery form and, if le_out != nullptr,
-// as 32 canonical little-endian bytes
-SHA_HD Fr challenge(uint8_t state[32], uint8_t* le_out) {
-    uint32_t st[8], nx[8];
-    sha::bytes_to_words(state, st);
-    Fr c = challenge_elem_w(st, 0);
-    sha::digest_state_suffix_w(st, 0x02, false, 0, nx);
-    sha::words_to_bytes(nx, state);
-    if (le_out) {
-        Fr plain = fr_from_mont(c);
-#pragma unroll
-        for (int l = 0; l < 8; ++l) {
-            le_out[4 * l] = (uint8_t)plain.v[l];
-            le_out[4 * l + 1] = (uint8_t)(plain.v[l] >> 8);
-            le_out[4 * l + 2] = (uint8_t)(plain.v[l] >> 16);
-            le_out[4 * l + 3] = (uint8_t)(plain.v[l] >> 24);
-        }
-    }
-    return c;
+// the stream extension that follows a draw
+SHA_HD void ratchet(State& s) {
+    uint8_t blk[64];
+    for (int i = 0; i < 64; ++i) blk[i] = 0;
+    blk[0] = 0xF2;
+    push_block(s, blk);
 }
 
 // canonical little-endian bytes of a Montgomery-form element
@@ -291,6 +326,21 @@ SHA_HD void fr_to_le(const Fr& mont, uint8_t out[32]) {
         out[4 * l + 2] = (uint8_t)(plain.v[l] >> 16);
         out[4 * l + 3] = (uint8_t)(plain.v[l] >> 24);
     }
+}
+
+// draw one challenge; returns it in Montgomery form and, if le_out != nullptr,
+// as 32 canonical little-endian bytes
+SHA_HD Fr challenge(State& s, uint8_t* le_out) {
+    Fr c = challenge_elem(s, 0);
+    ratchet(s);
+    if (le_out) fr_to_le(c, le_out);
+    return c;
+}
+
+SHA_HD void digest(const State& s, uint8_t out[32]) {
+    uint32_t w[8];
+    tail_digest_w(s, nullptr, 0, w);
+    sha::words_to_bytes(w, out);
 }
 
 }  // namespace ts

@@ -18,9 +18,10 @@ constexpr int ZK_BLOCK = 256;
 
 // Device-resident state of the call in flight.
 struct DevState {
-    uint32_t ts_state[8];   // transcript state: the SHA-256 digest as big-endian words
+    uint32_t ts_state[8];   // transcript: SHA-256 chaining value after the last block of the stream
     uint32_t err;           // bit 0: zkReLU input out of range
-    uint32_t pad0[7];
+    uint32_t ts_nblk[2];    // transcript: number of 64-byte blocks in the stream (low, high word)
+    uint32_t pad0[5];
     Fr claim;               // claim of the running sumcheck (Montgomery)
     Fr inv2, inv6;          // constants of the Lagrange formulas
     Fr weights[8];          // zkReLU: r^2, r, r'r^2, r'r, r'
@@ -42,7 +43,7 @@ struct zkdl_tensor {
 };
 
 struct zkdl_transcript {
-    uint8_t state[32];
+    ts::State s;
 };
 
 struct zkdl_ctx {

@@ -38,32 +38,101 @@ def test_field_basics():
         from_le(to_le(R_MOD - 1)[:-1] + b"\xff")
 
 
+def _sha256_compress(h, block):
+    """One application of the SHA-256 compression function (FIPS 180-4, Sec. 6.2.2)."""
+    def rotr(x, n):
+        return ((x >> n) | (x << (32 - n))) & 0xFFFFFFFF
+    # round constants: fractional parts of the cube roots of the first 64 primes
+    primes, c = [], 2
+    while len(primes) < 64:
+        if all(c % p for p in primes):
+            primes.append(c)
+        c += 1
+
+    def icbrt(n):
+        x = int(round(n ** (1.0 / 3)))
+        while x ** 3 > n:
+            x -= 1
+        while (x + 1) ** 3 <= n:
+            x += 1
+        return x
+    k = [icbrt(p << 96) & 0xFFFFFFFF for p in primes]
+    w = list(struct.unpack(">16I", block))
+    for t in range(16, 64):
+        s0 = rotr(w[t - 15], 7) ^ rotr(w[t - 15], 18) ^ (w[t - 15] >> 3)
+        s1 = rotr(w[t - 2], 17) ^ rotr(w[t - 2], 19) ^ (w[t - 2] >> 10)
+        w.append((w[t - 16] + s0 + w[t - 7] + s1) & 0xFFFFFFFF)
+    a, b, c_, d, e, f, g, hh = h
+    for t in range(64):
+        t1 = (hh + (rotr(e, 6) ^ rotr(e, 11) ^ rotr(e, 25)) + ((e & f) ^ (~e & g)) + k[t] + w[t]) & 0xFFFFFFFF
+        t2 = ((rotr(a, 2) ^ rotr(a, 13) ^ rotr(a, 22)) + ((a & b) ^ (a & c_) ^ (b & c_))) & 0xFFFFFFFF
+        a, b, c_, d, e, f, g, hh = (t1 + t2) & 0xFFFFFFFF, a, b, c_, (d + t1) & 0xFFFFFFFF, e, f, g
+    return [(x + y) & 0xFFFFFFFF for x, y in zip(h, (a, b, c_, d, e, f, g, hh))]
+
+
+_SHA256_IV = [0x6a09e667, 0xbb67ae85, 0x3c6ef372, 0xa54ff53a, 0x510e527f, 0x9b05688c, 0x1f83d9ab, 0x5be0cd19]
+
+
 def test_transcript_format():
     # SHA-256 itself: NIST "abc" vector through the same library call
     assert hashlib.sha256(b"abc").hexdigest() == \
         "ba7816bf8f01cfea414140de5dae2223b00361a396177a9cb410ff61f20015ad"
+    # every value is a one-shot hash of an explicitly written byte stream
     t = Transcript(9)
-    s0 = hashlib.sha256(b"zkdl-mi355x/v1" + struct.pack("<Q", 9)).digest()
-    assert t.digest() == s0
+    stream = b"zkdl-mi355x/v2" + b"\0" * 42 + struct.pack("<Q", 9)
+    assert len(stream) == 64 and t.digest() == hashlib.sha256(stream).digest()
     t.absorb(b"g", b"\x01\x02")
-    s1 = hashlib.sha256(s0 + b"\x01g" + struct.pack("<Q", 2) + b"\x01\x02").digest()
-    assert t.digest() == s1
+    stream += b"\x01g" + struct.pack("<Q", 2) + b"\x01\x02" + b"\0" * 52
+    assert len(stream) == 128 and t.digest() == hashlib.sha256(stream).digest()
     c = t.challenge()
     z4 = struct.pack("<I", 0)
-    wide = hashlib.sha256(s1 + b"\x00" + z4).digest() + hashlib.sha256(s1 + b"\x01" + z4).digest()
+    wide = hashlib.sha256(stream + b"\xf0" + z4).digest() + hashlib.sha256(stream + b"\xf1" + z4).digest()
     assert c == int.from_bytes(wide, "little") % R_MOD
-    s2 = hashlib.sha256(s1 + b"\x02").digest()
-    assert t.digest() == s2
+    s1 = stream
+    stream += b"\xf2" + b"\0" * 63
+    assert t.digest() == hashlib.sha256(stream).digest()
     assert t.challenge() != c
-    # a vector draw: index-derived elements, one state update
+    # a vector draw: index-derived elements, one stream extension
     t2 = Transcript(9)
     t2.absorb(b"g", b"\x01\x02")
     vec = t2.challenges_vec(3)
-    assert vec[0] == c and len(set(vec)) == 3 and t2.digest() == s2
+    assert vec[0] == c and len(set(vec)) == 3 and t2.digest() == hashlib.sha256(stream).digest()
     i2 = struct.pack("<I", 2)
-    wide = hashlib.sha256(s1 + b"\x00" + i2).digest() + hashlib.sha256(s1 + b"\x01" + i2).digest()
+    wide = hashlib.sha256(s1 + b"\xf0" + i2).digest() + hashlib.sha256(s1 + b"\xf1" + i2).digest()
     assert vec[2] == int.from_bytes(wide, "little") % R_MOD
-    assert t2.challenges_vec(0) == [] and t2.digest() == s2
+    assert t2.challenges_vec(0) == [] and t2.digest() == hashlib.sha256(stream).digest()
+    # frames longer than a block, a frame that fills its last block exactly, the longest label
+    t3 = Transcript(1)
+    s3 = b"zkdl-mi355x/v2" + b"\0" * 42 + struct.pack("<Q", 1)
+    for label, data in ((b"f", bytes(range(96))), (b"x", bytes(54)), (b"y" * 32, bytes(200)), (b"", b"")):
+        t3.absorb(label, data)
+        frame = bytes([len(label)]) + label + struct.pack("<Q", len(data)) + data
+        s3 += frame + b"\0" * (-len(frame) % 64)
+        assert len(s3) % 64 == 0 and t3.digest() == hashlib.sha256(s3).digest()
+    assert len(b"\x01x" + struct.pack("<Q", 54) + bytes(54)) == 64     # the exact-fit case above
+
+
+def test_transcript_draw_is_one_compression_from_the_chaining_value():
+    """The property the format is built for: the stream is block-aligned, so a challenge hash
+    is a single compression applied to the chaining value after the last absorbed block."""
+    assert b"".join(struct.pack(">I", x) for x in _sha256_compress(
+        _SHA256_IV, b"abc\x80" + b"\0" * 52 + struct.pack(">Q", 24))) == hashlib.sha256(b"abc").digest()
+    t = Transcript(5)
+    t.absorb_fr(b"g", [3, 4, 5])
+    blocks = b"zkdl-mi355x/v2" + b"\0" * 42 + struct.pack("<Q", 5)
+    frame = b"\x01g" + struct.pack("<Q", 96) + to_le(3) + to_le(4) + to_le(5)
+    blocks += frame + b"\0" * (128 - len(frame))
+    h = _SHA256_IV
+    for off in range(0, len(blocks), 64):
+        h = _sha256_compress(h, blocks[off:off + 64])
+    halves = []
+    for tag in (0xF0, 0xF1):
+        last = bytes([tag]) + struct.pack("<I", 0) + b"\x80" + b"\0" * 50 + struct.pack(">Q", 8 * (len(blocks) + 5))
+        halves.append(b"".join(struct.pack(">I", x) for x in _sha256_compress(h, last)))
+    assert t.challenge() == int.from_bytes(halves[0] + halves[1], "little") % R_MOD
+    h = _sha256_compress(h, b"\xf2" + b"\0" * 63)
+    fin = b"\x80" + b"\0" * 55 + struct.pack(">Q", 8 * (len(blocks) + 64))
+    assert t.digest() == b"".join(struct.pack(">I", x) for x in _sha256_compress(h, fin))
 
 
 def test_beta_table_boolean_points_are_one_hot_msb_first():

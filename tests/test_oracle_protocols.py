@@ -62,6 +62,31 @@ def test_product_sumcheck_against_brute_force(k, d):
     assert tv.digest() == ts.digest() and tv.challenges == ts.challenges
 
 
+def test_product_sumcheck_transcript_stream_written_out():
+    """The Fiat-Shamir schedule of a product sumcheck, rebuilt as one explicit byte stream from
+    the proof: header, claim_0, per round g_t without g_t(1), one draw per round, finals."""
+    import hashlib
+    import struct
+    k, d = 3, 3
+    tabs = [fr_array(rand_fr(1 << d)) for _ in range(k)]
+    ts = Transcript(12)
+    _, proof, vs = P.product_prove(tabs, ts)
+
+    def frame(label, data):
+        f = bytes([len(label)]) + label + struct.pack("<Q", len(data)) + data
+        return f + b"\0" * (-len(f) % 64)
+    stream = b"zkdl-mi355x/v2" + b"\0" * 42 + struct.pack("<Q", 12)
+    stream += frame(b"sumcheck_product", struct.pack("<II", k, d))
+    stream += frame(b"c", to_le(proof.claim0))
+    for t, g in enumerate(proof.rounds):
+        stream += frame(b"g", to_le(g[0]) + to_le(g[2]) + to_le(g[3]))
+        halves = [hashlib.sha256(stream + bytes([tag]) + struct.pack("<I", 0)).digest() for tag in (0xF0, 0xF1)]
+        assert vs[t] == int.from_bytes(halves[0] + halves[1], "little") % R_MOD
+        stream += b"\xf2" + b"\0" * 63
+    stream += frame(b"f", b"".join(to_le(x) for x in proof.finals))
+    assert ts.digest() == hashlib.sha256(stream).digest()
+
+
 def test_product_verifier_rejects_any_tampered_element():
     tabs = [fr_array(rand_fr(8)) for _ in range(3)]
     buf, _, _ = P.product_prove(tabs, Transcript(1))
