@@ -29,6 +29,23 @@
  *  - proof / proof_len: *proof_len holds the capacity in bytes on entry and the
  *    bytes written on return.  ZKDL_ESMALL sets *proof_len to the size needed.
  *
+ * Transcript (this library's own format).  The transcript is one byte stream,
+ * always a whole number of 64-byte blocks; every value derived from it is a
+ * plain SHA-256 of an extension of it:
+ *   stream_0         = "zkdl-mi355x/v2" zero-padded to 56 bytes || u64le(seed)
+ *   absorb(label, m) : stream <- stream || pad64(u8(|label|) || label ||
+ *                      u64le(|m|) || m), pad64 = zero bytes up to the next
+ *                      multiple of 64, |label| <= 32
+ *   challenges(n)    : c_i = int_le(SHA256(stream || 0xF0 || u32le(i)) ||
+ *                      SHA256(stream || 0xF1 || u32le(i))) mod r for i < n,
+ *                      then stream <- stream || 0xF2 || 63 zero bytes
+ *   digest           = SHA256(stream)
+ * Field elements are absorbed as zkdl_fr bytes.  A sumcheck absorbs its header
+ * words under the protocol's name, claim_0 under "c" (where the verifier cannot
+ * compute it), per round g_t(0), g_t(2), .., g_t(degree) under "g" (g_t(1) is
+ * fixed by the round check g_t(0) + g_t(1) = claim, Sec. 2.2) followed by a
+ * draw of one challenge, and the finals under "f".
+ *
  * Proof layout (all integers little-endian u32, all field elements zkdl_fr)
  *   SC block : "ZKSC", n_finals, degree, rounds, claim_0,
  *              rounds x (degree+1) evaluations g_t(0..degree), n_finals finals
@@ -77,7 +94,10 @@ const char* zkdl_strerror(int err);
 /* Frees cached scratch memory (the context keeps freed blocks for reuse). */
 int zkdl_ctx_trim(zkdl_ctx* ctx);
 
-/* ---- transcript (host side; format in the header comment of this file) --- */
+/* ---- transcript (host side; format in the header comment of this file) ---
+ * absorb: label is a NUL-terminated string of at most 32 bytes (ZKDL_EINVAL
+ * otherwise); host_bytes may be NULL when n is 0.  challenge: one draw of one
+ * element.  digest: SHA-256 of the stream so far; does not change the state. */
 int zkdl_transcript_create(zkdl_transcript** out, uint64_t seed);
 int zkdl_transcript_destroy(zkdl_transcript* t);
 int zkdl_transcript_absorb(zkdl_transcript* t, const char* label, const void* host_bytes, size_t n);
@@ -116,8 +136,8 @@ int mle_partial_eval(zkdl_ctx* ctx, const zkdl_tensor* t, int axis_lo, int axis_
  * sumcheck_product: sum over the hypercube of the product of K (1..3) Fr
  * tensors of equal numel 2^d, degree-K round polynomials (Sec. 2.2).  The
  * inputs are not modified.  finals (host, K elements, may be NULL): the tables'
- * evaluations at the challenge point.  Transcript: header, claim_0, then per
- * round g_t(0..K) and one challenge, then the finals.  Proof: one SC block. */
+ * evaluations at the challenge point.  Transcript: header "sumcheck_product"
+ * (K, d), claim_0, the rounds, the finals.  Proof: one SC block. */
 int sumcheck_product(zkdl_ctx* ctx, const zkdl_tensor* const* tables, int K, zkdl_transcript* tr,
                      uint8_t* proof, size_t* proof_len, zkdl_fr* finals, zkdl_fr* points_out,
                      size_t* npoints);

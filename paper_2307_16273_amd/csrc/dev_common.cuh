@@ -160,14 +160,14 @@ __device__ inline void block_absorb1(TsShared& S, char label, int count, bool dr
         } else {
             w = sha::draw_block_words(0xF0u + (threadIdx.x - nb), 0u, nblk_after);
         }
-        sha::schedule_wk_lds(w, S.wk[threadIdx.x]);
+        sha::schedule_wk_lds(w, (sha::lds_u32_ptr)S.wk[threadIdx.x]);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         sha::Words8 h;
 #pragma unroll
         for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
-        for (uint32_t blk = 0; blk < nb; ++blk) h = sha::rounds_lds(h, S.wk[blk]);
+        for (uint32_t blk = 0; blk < nb; ++blk) h = sha::rounds_lds(h, (sha::lds_u32_cptr)S.wk[blk]);
 #pragma unroll
         for (int i = 0; i < 8; ++i) S.state[i] = h.v[i];
         S.nblk = nblk_after;
@@ -289,7 +289,7 @@ __device__ inline Fr block_finalise_round(TsShared& S, DevState* st, const Fr* g
         sha::Words8 h;
 #pragma unroll
         for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
-        const sha::Words8 ow = sha::rounds_lds(h, S.wk[ts_frame_blocks(npts - 1) + tid]);
+        const sha::Words8 ow = sha::rounds_lds(h, (sha::lds_u32_cptr)S.wk[ts_frame_blocks(npts - 1) + tid]);
         if (tid < 2) {
             Fr x;
 #pragma unroll
@@ -313,26 +313,24 @@ __device__ inline Fr block_finalise_round(TsShared& S, DevState* st, const Fr* g
     if (tid < 8) S.state[tid] = S.dig[2][tid];
     if (tid == 8) S.nblk += 1;
     if (tid == 0) st->chal[chal_idx] = v;
-    // first level of the Lagrange sum (wave 0, one product per lane) | canonical v (wave 1)
+    // first level of the Lagrange sum (wave 0, one product per lane) | canonical v (wave 1).
+    // The operands are selected per lane and multiplied by one call: lanes that branch to
+    // separate calls would run them one after the other.
     const Fr one = fr_one();
     const Fr v1 = fr_sub(v, one), v2 = fr_sub(v1, one), v3 = fr_sub(v2, one);
     if (tid < 6) {
-        Fr p = fr_zero();
+        // npts = 4: c0 (v-1), c1 v, c2 (v-3), c3 (v-2), (v-2)(v-3), v (v-1)
+        // npts = 3: c0 (v-1), c1 v, c2 v;   npts = 2: c0 (v-1), c1 v
+        Fr A = tid == 4 ? v2 : v;
+        if (tid < 4) A = S.tmp[tid];
+        Fr B = tid == 1 ? v : v1;                // lanes 0, 1, and lane 5: v - 1
         if (npts == 4) {
-            if (tid == 0) p = fr_mul_ni(S.tmp[0], v1);
-            else if (tid == 1) p = fr_mul_ni(S.tmp[1], v);
-            else if (tid == 2) p = fr_mul_ni(S.tmp[2], v3);
-            else if (tid == 3) p = fr_mul_ni(S.tmp[3], v2);
-            else if (tid == 4) p = fr_mul_ni(v2, v3);
-            else p = fr_mul_ni(v, v1);
-        } else if (npts == 3) {
-            if (tid == 0) p = fr_mul_ni(S.tmp[0], v1);
-            else if (tid == 1) p = fr_mul_ni(S.tmp[1], v);
-            else if (tid == 2) p = fr_mul_ni(S.tmp[2], v);
-        } else {
-            if (tid == 0) p = fr_mul_ni(S.tmp[0], v1);
-            else if (tid == 1) p = fr_mul_ni(S.tmp[1], v);
+            if (tid == 2 || tid == 4) B = v3;
+            else if (tid == 3) B = v2;
+        } else if (tid == 2) {
+            B = v;
         }
+        const Fr p = fr_mul_ni(A, B);
 #pragma unroll
         for (int l = 0; l < 8; ++l) S.dig[4 + tid][l] = p.v[l];
     } else if (tid == 64) {
@@ -349,9 +347,20 @@ __device__ inline Fr block_finalise_round(TsShared& S, DevState* st, const Fr* g
 #pragma unroll
             for (int l = 0; l < 8; ++l) q[j].v[l] = S.dig[4 + j][l];
         Fr r;
-        if (npts == 4) r = tid == 0 ? fr_mul_ni(q[4], fr_add(q[0], q[1])) : fr_mul_ni(q[5], fr_add(q[2], q[3]));
-        else if (npts == 3) r = tid == 0 ? fr_mul_ni(v2, fr_add(q[0], q[1])) : fr_mul_ni(q[2], v1);
-        else r = tid == 0 ? fr_add(q[0], q[1]) : fr_zero();
+        if (npts == 2) {
+            r = tid == 0 ? fr_add(q[0], q[1]) : fr_zero();
+        } else {
+            // npts = 4: (v-2)(v-3) [q0 + q1], v (v-1) [q2 + q3];  npts = 3: (v-2) [q0 + q1], q2 (v-1)
+            Fr A, B;
+            if (npts == 4) {
+                A = tid == 0 ? q[4] : q[5];
+                B = tid == 0 ? fr_add(q[0], q[1]) : fr_add(q[2], q[3]);
+            } else {
+                A = tid == 0 ? v2 : q[2];
+                B = tid == 0 ? fr_add(q[0], q[1]) : v1;
+            }
+            r = fr_mul_ni(A, B);
+        }
 #pragma unroll
         for (int l = 0; l < 8; ++l) S.dig[10 + tid][l] = r.v[l];
     }

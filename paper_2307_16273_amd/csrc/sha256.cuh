@@ -101,6 +101,24 @@ static __device__ const uint32_t K_TABLE[64] = {
     0x19a4c116, 0x1e376c08, 0x2748774c, 0x34b0bcb5, 0x391c0cb3, 0x4ed8aa4a, 0x5b9cca4f, 0x682e6ff3,
     0x748f82ee, 0x78a5636f, 0x84c87814, 0x8cc70208, 0x90befffa, 0xa4506ceb, 0xbef9a3f7, 0xc67178f2};
 
+// three-input bit operations in one instruction (truth table in the immediate)
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+__device__ __forceinline__ uint32_t choose(uint32_t e, uint32_t f, uint32_t g) {   // e ? f : g
+    return __builtin_amdgcn_bitop3_b32(e, f, g, 0xCA);
+}
+__device__ __forceinline__ uint32_t majority(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0xE8);
+}
+__device__ __forceinline__ uint32_t big_sigma1(uint32_t e) { return xor3(rotr(e, 6), rotr(e, 11), rotr(e, 25)); }
+__device__ __forceinline__ uint32_t big_sigma0(uint32_t a) { return xor3(rotr(a, 2), rotr(a, 13), rotr(a, 22)); }
+__device__ __forceinline__ uint32_t small_sigma0(uint32_t w) { return xor3(rotr(w, 7), rotr(w, 18), w >> 3); }
+__device__ __forceinline__ uint32_t small_sigma1(uint32_t w) { return xor3(rotr(w, 17), rotr(w, 19), w >> 10); }
+
+typedef __attribute__((address_space(3))) uint32_t* lds_u32_ptr;
+typedef const __attribute__((address_space(3))) uint32_t* lds_u32_cptr;
+
 static __device__ __noinline__ Words8 compress_ni(Words8 hin, Words16 win) {
     uint32_t w[16];
 #pragma unroll
@@ -111,19 +129,10 @@ static __device__ __noinline__ Words8 compress_ni(Words8 hin, Words16 win) {
     for (int r = 0; r < 4; ++r) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            if (r > 0) {
-                uint32_t w15 = w[(i + 1) & 15], w2 = w[(i + 14) & 15];
-                uint32_t s0 = rotr(w15, 7) ^ rotr(w15, 18) ^ (w15 >> 3);
-                uint32_t s1 = rotr(w2, 17) ^ rotr(w2, 19) ^ (w2 >> 10);
-                w[i] = w[i] + s0 + w[(i + 9) & 15] + s1;
-            }
-            uint32_t S1 = rotr(e, 6) ^ rotr(e, 11) ^ rotr(e, 25);
-            uint32_t ch = (e & f) | (~e & g);
-            uint32_t t1 = hh + S1 + ch + K_TABLE[16 * r + i] + w[i];
-            uint32_t S0 = rotr(a, 2) ^ rotr(a, 13) ^ rotr(a, 22);
-            uint32_t ab = a ^ b;
-            uint32_t mj = (ab & c) | (~ab & b);
-            hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + S0 + mj;
+            if (r > 0) w[i] = w[i] + small_sigma0(w[(i + 1) & 15]) + w[(i + 9) & 15] + small_sigma1(w[(i + 14) & 15]);
+            uint32_t t1 = hh + big_sigma1(e) + choose(e, f, g) + K_TABLE[16 * r + i] + w[i];
+            uint32_t t2 = big_sigma0(a) + majority(a, b, c);
+            hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + t2;
         }
     }
     Words8 o;
@@ -139,7 +148,7 @@ __device__ inline Words8 iv_words() {
 }
 
 // wk[0..64) = W[t] + K[t] of one block, written to LDS; compact (one 16-step loop body)
-static __device__ __noinline__ void schedule_wk_lds(Words16 win, uint32_t* wk) {
+static __device__ __noinline__ void schedule_wk_lds(Words16 win, lds_u32_ptr wk) {
     uint32_t w[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -150,34 +159,34 @@ static __device__ __noinline__ void schedule_wk_lds(Words16 win, uint32_t* wk) {
     for (int r = 1; r < 4; ++r) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            uint32_t w15 = w[(i + 1) & 15], w2 = w[(i + 14) & 15];
-            uint32_t s0 = rotr(w15, 7) ^ rotr(w15, 18) ^ (w15 >> 3);
-            uint32_t s1 = rotr(w2, 17) ^ rotr(w2, 19) ^ (w2 >> 10);
-            w[i] = w[i] + s0 + w[(i + 9) & 15] + s1;
+            w[i] = w[i] + small_sigma0(w[(i + 1) & 15]) + w[(i + 9) & 15] + small_sigma1(w[(i + 14) & 15]);
             wk[16 * r + i] = w[i] + K_TABLE[16 * r + i];
         }
     }
 }
 
-// the 64 rounds on a schedule prepared in LDS; compact (one 8-round loop body)
-static __device__ __noinline__ Words8 rounds_lds(Words8 hin, const uint32_t* wk) {
+// the 64 rounds on a schedule prepared in LDS; compact (one 8-round loop body); the
+// next eight schedule words are fetched while the current eight rounds run
+static __device__ __noinline__ Words8 rounds_lds(Words8 hin, lds_u32_cptr wk) {
     uint32_t a = hin.v[0], b = hin.v[1], c = hin.v[2], d = hin.v[3], e = hin.v[4], f = hin.v[5],
              g = hin.v[6], hh = hin.v[7];
+    uint32_t x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = wk[i];
 #pragma unroll 1
     for (int r = 0; r < 8; ++r) {
-        uint32_t x[8];
+        uint32_t nx[8];
+        const int nr = (r + 1) & 7;   // the last fetch wraps to the first words and is dropped
 #pragma unroll
-        for (int i = 0; i < 8; ++i) x[i] = wk[8 * r + i];
+        for (int i = 0; i < 8; ++i) nx[i] = wk[8 * nr + i];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            uint32_t S1 = rotr(e, 6) ^ rotr(e, 11) ^ rotr(e, 25);
-            uint32_t ch = (e & f) | (~e & g);
-            uint32_t t1 = hh + S1 + ch + x[i];
-            uint32_t S0 = rotr(a, 2) ^ rotr(a, 13) ^ rotr(a, 22);
-            uint32_t ab = a ^ b;
-            uint32_t mj = (ab & c) | (~ab & b);
-            hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + S0 + mj;
+            uint32_t t1 = hh + big_sigma1(e) + choose(e, f, g) + x[i];
+            uint32_t t2 = big_sigma0(a) + majority(a, b, c);
+            hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + t2;
         }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = nx[i];
     }
     Words8 o;
     o.v[0] = hin.v[0] + a; o.v[1] = hin.v[1] + b; o.v[2] = hin.v[2] + c; o.v[3] = hin.v[3] + d;
