@@ -477,7 +477,156 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat2(BinArgs a) {
     }
 }
 
-// Rounds t >= 2 on the materialised columns (lazy limbs, same invariants as the product
+// ---- round 2 by look-up as well -------------------------------------------------------
+// With x0 = v0 and x1 = v1 bound an entry is one of the 16 values above, so the pair that
+// round 2 interpolates is one of 256 combinations and q(x) = e(x)^2 - e(x) is a table of
+// 256 entries per evaluation point, built once per block in LDS.  Per column that leaves
+// a table read and the product with beta_J, accumulated as 64-bit columns.  The rows of
+// pair index i3 (m = D/8 of them) are i3 + s m, s = 4 x0 + 2 x1 + x2.
+
+// 16-value code of the entry at x2 from bit j of the eight rows (w[s] already shifted so
+// that bit j is bit 0): bits (x0,x1) = (0,0), (1,0), (0,1), (1,1) as in k_zk_mat2
+__device__ __forceinline__ uint32_t pair_code8(const uint64_t w[8]) {
+    const uint32_t lo = ((uint32_t)w[0] & 1u) | (((uint32_t)w[4] & 1u) << 1) | (((uint32_t)w[2] & 1u) << 2) |
+                        (((uint32_t)w[6] & 1u) << 3);
+    const uint32_t hi = ((uint32_t)w[1] & 1u) | (((uint32_t)w[5] & 1u) << 1) | (((uint32_t)w[3] & 1u) << 2) |
+                        (((uint32_t)w[7] & 1u) << 3);
+    return lo | (hi << 4);
+}
+
+// the 16 values of an entry after v0, v1 (lazy limbs, normal, fully reduced)
+__device__ __forceinline__ void bound2_values(const Fr* chal, F9* val16) {
+    if (threadIdx.x < 16) {
+        const int c = threadIdx.x;
+        const Fr v0 = chal[0], v1 = chal[1], one = fr_one();
+        const Fr alo = bit_pair_value(c & 3, v0, one), ahi = bit_pair_value(c >> 2, v0, one);
+        val16[c] = fr_unpack(fr_add(alo, fr_mul(v1, fr_sub(ahi, alo))));
+    }
+}
+
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin2(BinArgs a) {
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    __shared__ F9 sbj[2][64];
+    __shared__ F9 val16[16];
+    __shared__ uint32_t qlut[3][9][256];   // q(x) at x = 0, 2, 3 by combination, limb-major
+    const int tid = threadIdx.x;
+    if (tid < 128) {
+        const int j = tid & 63, k = tid >> 6;
+        F9 x = f9_zero();
+        if (j < a.nbits) x = fr_unpack(k == 0 ? a.bJ[j] : fr_mul(*a.rp, a.bJ[j]));
+        sbj[k][j] = x;
+    }
+    bound2_values(a.chal, val16);
+    __syncthreads();
+    {
+        const F9 one9 = fr_unpack(fr_one());
+        const F9 lo = val16[tid & 15], hi = val16[tid >> 4];
+        const F9 dn = f9_norm(f9_sub(hi, lo));
+        F9 e[3];
+        e[0] = lo;
+        e[1] = f9_norm(f9_add(hi, dn));
+        e[2] = f9_norm(f9_add(e[1], dn));
+#pragma unroll
+        for (int x = 0; x < 3; ++x) {
+            const F9 q = f9_mul(e[x], f9_sub(e[x], one9));
+#pragma unroll
+            for (int l = 0; l < 9; ++l) qlut[x][l][tid] = q.v[l];
+        }
+    }
+    __syncthreads();
+    const uint64_t m = a.m;
+    int j0 = blockIdx.y * a.jc, j1 = j0 + a.jc;
+    if (j1 > a.nbits) j1 = a.nbits;
+    F9 tot[3];
+#pragma unroll
+    for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+        uint64_t cols[3][17];
+#pragma unroll
+        for (int x = 0; x < 3; ++x)
+#pragma unroll
+            for (int c = 0; c < 17; ++c) cols[x][c] = 0;
+        int pending = 0;
+        for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+            const int64_t* src = k == 0 ? a.z : a.ga;
+            uint64_t w[8];
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2) w[s2] = (uint64_t)src[b + (uint64_t)s2 * m] >> j0;
+            for (int j = j0; j < j1; ++j) {
+                const uint32_t C = pair_code8(w);
+#pragma unroll
+                for (int s2 = 0; s2 < 8; ++s2) w[s2] >>= 1;
+                const F9 bj = sbj[k][j];
+#pragma unroll
+                for (int x = 0; x < 3; ++x) {
+                    F9 q;
+#pragma unroll
+                    for (int l = 0; l < 9; ++l) q.v[l] = qlut[x][l][C];
+                    f9_cols_mac(cols[x], bj, q);
+                }
+                if (++pending == 4) {
+                    pending = 0;
+#pragma unroll
+                    for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
+                }
+            }
+        }
+        F9 bi[3];
+        beta_line(a.bI, b, m, bi);
+#pragma unroll
+        for (int x = 0; x < 3; ++x) {
+            f9_cols_norm<17>(cols[x]);
+            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_redc(cols[x]))));
+        }
+    }
+    const uint64_t blk = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    {
+        const Fr s = block_sum_lazy<3>(tot, red);
+        Fr* p = a.part + blk * 4;
+        if (tid < 3) p[tid ? tid + 1 : 0] = s;
+        else if (tid == 3) p[1] = fr_zero();
+    }
+}
+
+// After the third challenge: entry (k, v0, v1, v2, i3, j) = lo + v2 (hi - lo), one of 256
+// values by the eight bits; written as lazy limbs, D/8 rows per column.
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat3(BinArgs a) {
+    __shared__ F9 val16[16];
+    __shared__ uint32_t vlut[9][256];
+    const int tid = threadIdx.x;
+    bound2_values(a.chal, val16);
+    __syncthreads();
+    {
+        const F9 v2 = fr_unpack(a.chal[2]);
+        const F9 lo = val16[tid & 15], hi = val16[tid >> 4];
+        const F9 f = f9_norm_reduce(f9_add(lo, f9_mul(f9_sub(hi, lo), v2)));
+#pragma unroll
+        for (int l = 0; l < 9; ++l) vlut[l][tid] = f.v[l];
+    }
+    __syncthreads();
+    const uint64_t m = a.m;   // rows written = D / 8
+    int j0 = blockIdx.y * a.jc, j1 = j0 + a.jc;
+    if (j1 > a.nbits) j1 = a.nbits;
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+        for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+            const int64_t* src = k == 0 ? a.z : a.ga;
+            uint64_t w[8];
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2) w[s2] = (uint64_t)src[b + (uint64_t)s2 * m] >> j0;
+            for (int j = j0; j < j1; ++j) {
+                const uint32_t C = pair_code8(w);
+#pragma unroll
+                for (int s2 = 0; s2 < 8; ++s2) w[s2] >>= 1;
+                F9 f;
+#pragma unroll
+                for (int l = 0; l < 9; ++l) f.v[l] = vlut[l][C];
+                f9tab_st(aux_col9(a, k, j), b, f);
+            }
+        }
+    }
+}
+
+// Rounds after the materialisation, on the columns in memory (lazy limbs, same invariants as the product
 // round kernel): per (i', j, slice) the pair (lo, hi), folded with the previous challenge
 // first when FOLD; q(x) = e(x) (e(x) - 1) at x = 0, 2, 3; per thread the sum over its columns
 // of beta_J(j) q(x) (slice 1 with r' beta_J), then times beta_I(x, i').
@@ -503,9 +652,12 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_binl(BinArgs a) {
 #pragma unroll
     for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
     for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
-        F9 acc[3];
+        // sum over the columns of beta_J(j) q(x) as 64-bit columns: one reduction per (i', x)
+        uint64_t cols[3][17];
 #pragma unroll
-        for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
+        for (int x = 0; x < 3; ++x)
+#pragma unroll
+            for (int c = 0; c < 17; ++c) cols[x][c] = 0;
         int pending = 0;
         for (int j = j0; j < j1; ++j) {
             for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
@@ -530,22 +682,25 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_binl(BinArgs a) {
                 const F9 bj = sbj[k][j];
 #pragma unroll
                 for (int x = 0; x < 3; ++x) {
-                    // e (e - 1): e normal, e - 1 + 4r has limbs < 2^29 + 2^30
+                    // e (e - 1): e normal, e - 1 + 4r has limbs < 2^29 + 2^30; the product is normal
                     const F9 q = f9_mul(e[x], f9_sub(e[x], one9));
-                    acc[x] = f9_add(acc[x], f9_mul(bj, q));
+                    f9_cols_mac(cols[x], bj, q);
                 }
-                if (++pending == 2) {
+                if (++pending == 4) {
                     pending = 0;
 #pragma unroll
-                    for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
+                    for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
                 }
             }
         }
         F9 bi[3];
         beta_line(a.bI, b, m, bi);
 #pragma unroll
-        for (int x = 0; x < 3; ++x)
-            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_norm_reduce(acc[x]))));
+        for (int x = 0; x < 3; ++x) {
+            // at most 128 products below 2 r^2 each: the reduced sum is below 4.8 r, normal
+            f9_cols_norm<17>(cols[x]);
+            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_redc(cols[x]))));
+        }
     }
     const uint64_t blk = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
     {
@@ -563,6 +718,7 @@ struct TailArgs {
     ZkTabs tabs;
     BinArgs bin;          // aux planes, z/ga, bJ
     int li, lj, q_bits, r_bits;
+    int mat_bound;        // i-challenges bound when the aux columns were written (2 or 3)
     DevState* st;
     int chal_v;           // index of the first round challenge (i-rounds, then j-rounds)
     int chal_rho;         // rho0..2, then the merge challenges
@@ -636,10 +792,11 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
                 const int code = (int)(((uint64_t)src[0] >> j) & 1) | (int)((((uint64_t)src[1] >> j) & 1) << 1);
                 val = bit_pair_value(code, vlast, one);
             } else {
-                // the columns were written after the second challenge; later rounds folded them
+                // the columns were written with mat_bound challenges bound; later rounds
+                // folded them down to two rows
                 F9Tab col = aux_col9(a.bin, k, j);
                 val = f9_to_fr(f9tab_ld(col, 0));
-                if (a.li >= 3) {
+                if (a.li > a.mat_bound) {
                     Fr hi = f9_to_fr(f9tab_ld(col, 1));
                     val = fr_add(val, fr_mul_ni(vlast, fr_sub(hi, val)));
                 }
@@ -881,8 +1038,10 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     DevState* st = ctx->dev;
     zk_launch_draw(ctx, c0, 5 * li + lj);
 
-    // memory: 10 D-sized tables, beta_J, aux columns (2 * nbits columns of D/4 rows, 36 B entries)
-    const uint64_t rows = D >= 4 ? D / 4 : 1;
+    // memory: 10 D-sized tables, beta_J, aux columns (2 * nbits columns of 36 B entries; the rows
+    // are written once three challenges are bound, D/8 of them; two challenges if D = 4)
+    const int mat_bound = li >= 3 ? 3 : 2;
+    const uint64_t rows = li >= 3 ? D / 8 : 1;
     const uint64_t aux_elems = (uint64_t)(has_ga ? 2 : 1) * nbits * rows;
     void* mem = zk_alloc(ctx, (uint64_t)LIN_TABLES * D * 36 + 64 * 32 + (li >= 2 ? aux_elems * 36 : 0));
     void* beta_mem = zk_alloc(ctx, (uint64_t)5 * D * 32);
@@ -996,25 +1155,36 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
             unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
             unsigned bx = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / chunks);
             ba.jc = jc;
-            ba.chal = t >= 3 ? &st->chal[c_v + t - 1] : nullptr;
-            zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN,
-                          (has_ga ? 2.0 : 1.0) * nbits * (t >= 3 ? 192.0 : 64.0) * (double)m + 64.0 * (double)m);
-            if (t >= 3) hipLaunchKernelGGL(k_zk_binl<true>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
-            else hipLaunchKernelGGL(k_zk_binl<false>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
-            zk_prof_end(ctx);
+            if (t == 2) {
+                // third round: look-up again, on the eight rows of a pair index
+                ba.chal = &st->chal[c_v];
+                zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, (has_ga ? 128.0 : 64.0) * (double)m + 64.0 * (double)m);
+                hipLaunchKernelGGL(k_zk_bin2, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+                zk_prof_end(ctx);
+            } else {
+                ba.chal = t >= 4 ? &st->chal[c_v + t - 1] : nullptr;
+                zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN,
+                              (has_ga ? 2.0 : 1.0) * nbits * (t >= 4 ? 216.0 : 72.0) * (double)m + 64.0 * (double)m);
+                if (t >= 4) hipLaunchKernelGGL(k_zk_binl<true>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+                else hipLaunchKernelGGL(k_zk_binl<false>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+                zk_prof_end(ctx);
+            }
             nb_bin = bx * chunks;
         }
         // g(1) is taken from the running claim: the binarity kernels leave it out
         zk_launch_finalise(ctx, (int)(nb_lin + nb_bin), 4, c_v + t, rounds_off + (uint32_t)t * 128, 0, 0, 1);
-        if (t == 1) {
-            // bind the first two challenges: bits -> field elements, D/4 rows per column
+        if (t + 1 == mat_bound) {
+            // bind the first challenges: bits -> field elements, one look-up per entry
             int jc = nbits;
             while ((uint64_t)((nbits + jc - 1) / jc) * m < 32768 && jc > 1) jc = (jc + 1) / 2;
             unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
             ba.jc = jc;
             ba.chal = &st->chal[c_v];
             ba.m = m;
-            hipLaunchKernelGGL(k_zk_mat2, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            if (mat_bound == 2)
+                hipLaunchKernelGGL(k_zk_mat2, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            else
+                hipLaunchKernelGGL(k_zk_mat3, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
         }
     }
     TailArgs ta;
@@ -1022,6 +1192,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     ta.bin = ba;
     ta.li = li;
     ta.lj = lj;
+    ta.mat_bound = mat_bound;
     ta.q_bits = Q;
     ta.r_bits = R;
     ta.st = st;
