@@ -460,44 +460,11 @@ void zk_write_proof_words(zkdl_ctx* ctx, const uint32_t* words, int n) {
     ctx->proof_len += 4 * (size_t)n;
 }
 
-struct AbsorbWordsArg {
-    char label[32];
-    uint32_t label_len;
-    uint32_t words[8];
-    uint32_t n;
-};
-
-__global__ void k_absorb_words(DevState* st, AbsorbWordsArg a) {
-    if (threadIdx.x != 0) return;
-    uint8_t data[32];
-    for (uint32_t i = 0; i < a.n; ++i)
-        for (int b = 0; b < 4; ++b) data[4 * i + b] = (uint8_t)(a.words[i] >> (8 * b));
-    ts::State s;
-    for (int i = 0; i < 8; ++i) s.h[i] = st->ts_state[i];
-    s.nblk = ((uint64_t)st->ts_nblk[1] << 32) | st->ts_nblk[0];
-    ts::absorb(s, a.label, a.label_len, data, 4 * a.n);
-    for (int i = 0; i < 8; ++i) st->ts_state[i] = s.h[i];
-    st->ts_nblk[0] = (uint32_t)s.nblk;
-    st->ts_nblk[1] = (uint32_t)(s.nblk >> 32);
-}
-
-// header of a protocol: a label and up to 8 little-endian u32 words, absorbed in stream order
-static void dev_absorb_words(zkdl_ctx* ctx, const char* label, const uint32_t* words, int n) {
-    AbsorbWordsArg a;
-    a.label_len = 0;
-    while (label[a.label_len] && a.label_len < 31) {
-        a.label[a.label_len] = label[a.label_len];
-        ++a.label_len;
-    }
-    a.n = (uint32_t)n;
-    for (int i = 0; i < n; ++i) a.words[i] = words[i];
-    hipLaunchKernelGGL(k_absorb_words, dim3(1), dim3(64), 0, ctx->stream, ctx->dev, a);
-}
-
 static int call_begin(zkdl_ctx* ctx, zkdl_transcript* tr) {
     ZK_HIP(ctx, hipSetDevice(ctx->device));
     ctx->n_chal = 0;
     ctx->proof_len = 0;
+    ctx->pend_len = 0;
     g_patches.clear();
     // state + cleared error word
     memset(ctx->host_stage, 0, 64);
@@ -511,9 +478,17 @@ static int call_begin(zkdl_ctx* ctx, zkdl_transcript* tr) {
     return ZKDL_OK;
 }
 
-static int call_end(zkdl_ctx* ctx, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+// rc_in: result of the enqueue phase; on failure the stream is drained and the caller's
+// transcript and buffers stay as they were
+static int call_end(zkdl_ctx* ctx, zkdl_transcript* tr, int rc_in, uint8_t* proof, size_t* proof_len,
                     zkdl_fr* points_out, size_t* npoints, const int* scal_ids, int n_scal,
                     zkdl_fr* scal_out) {
+    if (rc_in != ZKDL_OK) {
+        ctx->pend_len = 0;
+        ZK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        return rc_in;
+    }
+    zk_flush_frames(ctx);
     ZK_HIP(ctx, hipGetLastError());
     uint8_t* hs = ctx->host_stage;
     // layout of the staging buffer mirrors DevState
@@ -632,7 +607,7 @@ extern "C" int sumcheck_product(zkdl_ctx* ctx, const zkdl_tensor* const* tables,
     int rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
     uint32_t hdr[2] = {(uint32_t)K, (uint32_t)d};
-    dev_absorb_words(ctx, "sumcheck_product", hdr, 2);
+    zk_absorb_words(ctx, "sumcheck_product", hdr, 2);
     FrView views[3];
     FrTab src[3];
     void* wmem = nullptr;
@@ -647,7 +622,7 @@ extern "C" int sumcheck_product(zkdl_ctx* ctx, const zkdl_tensor* const* tables,
     }
     if (rc == ZKDL_OK) rc = zk_sumcheck_product(ctx, K, src, wmem, d, 0);
     int ids[3] = {0, 1, 2};
-    int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, ids, K, finals);
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, K, finals);
     zk_free(ctx, wmem);
     for (int k = 0; k < K; ++k) zk_free(ctx, views[k].scratch);
     return rc != ZKDL_OK ? rc : rc2;
@@ -677,22 +652,23 @@ static int enqueue_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tenso
     const int ln = ilog2_u64(N), l1 = ilog2_u64(D1), l2 = ilog2_u64(D2), l3 = ilog2_u64(D3);
     if (ctx->n_chal + ln + l1 + l3 + ln + l2 > ZK_MAX_CHAL) return ZKDL_EINVAL;
     uint32_t hdr[4] = {(uint32_t)N, (uint32_t)D1, (uint32_t)D2, (uint32_t)D3};
-    dev_absorb_words(ctx, "sumcheck_matmul", hdr, 4);
+    zk_absorb_words(ctx, "sumcheck_matmul", hdr, 4);
     const int cw = ctx->n_chal, cu0 = cw + ln, cu1 = cu0 + l1;
     zk_launch_draw(ctx, cw, ln + l1 + l3);
     ctx->n_chal += ln + l1 + l3;
     const Fr* chal = ctx->dev->chal;
 
     const uint64_t len = N * D2;
-    const uint64_t bmax = D1 > D3 ? D1 : D3;
-    // scratch: beta tables (N, max(D1,D3)), three source tables, one shift temp, the work tables
-    void* mem = zk_alloc(ctx, (N + bmax + 4 * len) * 32 + zk_sumcheck_work_bytes(3, ln + l2));
+    // scratch: beta tables (N, D1, D3), three source tables, one shift temp, the work tables
+    void* mem = zk_alloc(ctx, (N + D1 + D3 + 4 * len) * 32 + zk_sumcheck_work_bytes(3, ln + l2));
     if (!mem) return ZKDL_ENOMEM;
     uint32_t* base = (uint32_t*)mem;
     FrTab bw = make_tab(base, N);
     base += 8 * N;
-    FrTab bu = make_tab(base, bmax);
-    base += 8 * bmax;
+    FrTab bu0 = make_tab(base, D1);
+    base += 8 * D1;
+    FrTab bu1 = make_tab(base, D3);
+    base += 8 * D3;
     FrTab src[3];
     for (int k = 0; k < 3; ++k) {
         src[k] = make_tab(base, len);
@@ -701,26 +677,25 @@ static int enqueue_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tenso
     FrTab tmp = make_tab(base, len);
     base += 8 * len;
     void* work = base;
-    int rc = zk_build_beta(ctx, chal + cw, ln, bw);
+    const BetaJob bjobs[3] = {{chal + cw, ln, bw}, {chal + cu0, l1, bu0}, {chal + cu1, l3, bu1}};
+    int rc = zk_build_beta_many(ctx, bjobs, 3);
     if (rc == ZKDL_OK) zk_launch_broadcast_rows(ctx, bw, N, D2, src[0]);
     // T0[n, i] = X0~(n, u0, i): bind the D1 axis of op(X0)
-    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, chal + cu0, l1, bu);
     if (rc == ZKDL_OK) {
         FrTab s0 = make_tab(X0->data, X0->numel);
         const void* sp = X0->kind == TK_FR ? (const void*)&s0 : X0->data;
         FrTab dst = shift ? tmp : src[1];
-        if (!tr0) rc = zk_partial_eval(ctx, X0->kind, sp, N, D1, D2, bu, dst);       // stored [N, D1, D2]
-        else rc = zk_partial_eval(ctx, X0->kind, sp, N * D2, D1, 1, bu, dst);        // stored [N, D2, D1]
+        if (!tr0) rc = zk_partial_eval(ctx, X0->kind, sp, N, D1, D2, bu0, dst);      // stored [N, D1, D2]
+        else rc = zk_partial_eval(ctx, X0->kind, sp, N * D2, D1, 1, bu0, dst);       // stored [N, D2, D1]
         if (rc == ZKDL_OK && shift) zk_launch_shift_rows(ctx, tmp, N, D2, shift, src[1]);
     }
     // T1[n, i] = X1~(n, i, u1): bind the D3 axis of op(X1)
-    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, chal + cu1, l3, bu);
     if (rc == ZKDL_OK) {
         FrTab s1 = make_tab(X1->data, X1->numel);
         const void* sp = X1->kind == TK_FR ? (const void*)&s1 : X1->data;
         FrTab dst = shift ? tmp : src[2];
-        if (!tr1) rc = zk_partial_eval(ctx, X1->kind, sp, N * D2, D3, 1, bu, dst);   // stored [N, D2, D3]
-        else rc = zk_partial_eval(ctx, X1->kind, sp, N, D3, D2, bu, dst);            // stored [N, D3, D2]
+        if (!tr1) rc = zk_partial_eval(ctx, X1->kind, sp, N * D2, D3, 1, bu1, dst);  // stored [N, D2, D3]
+        else rc = zk_partial_eval(ctx, X1->kind, sp, N, D3, D2, bu1, dst);           // stored [N, D3, D2]
         if (rc == ZKDL_OK && shift) zk_launch_shift_rows(ctx, tmp, N, D2, shift, src[2]);
     }
     if (rc == ZKDL_OK) rc = zk_sumcheck_product(ctx, 3, src, work, ln + l2, scal_base);
@@ -738,7 +713,7 @@ extern "C" int sumcheck_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_
     rc = enqueue_matmul(ctx, X0, X1, transpose_x0 != 0, transpose_x1 != 0, 0, 0, nullptr);
     zkdl_fr tmp[3];
     int ids[3] = {0, 1, 2};
-    int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, ids, 3, tmp);
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 3, tmp);
     if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims && proof) {
         memcpy(claims[0].le, proof + 16, 32);   // claim_0 = Y~(w, u0, u1)
         claims[1] = tmp[1];
@@ -757,7 +732,7 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
     int rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
     uint32_t hdr[1] = {(uint32_t)d};
-    dev_absorb_words(ctx, "sumcheck_hadamard", hdr, 1);
+    zk_absorb_words(ctx, "sumcheck_hadamard", hdr, 1);
     zk_launch_draw(ctx, 0, d);
     ctx->n_chal = d;
     FrView v0, v1;
@@ -774,7 +749,7 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
     }
     zkdl_fr tmp[3];
     int ids[3] = {0, 1, 2};
-    int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, ids, 3, tmp);
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 3, tmp);
     if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims && proof) {
         memcpy(claims[0].le, proof + 16, 32);
         claims[1] = tmp[1];
@@ -807,7 +782,7 @@ static int enqueue_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga
                           int R) {
     if (!is_pow2(D) || Q < 1 || R < 1 || Q + R > 64 || Q + R < 2) return ZKDL_EINVAL;
     uint32_t hw[4] = {(uint32_t)ilog2_u64(D), (uint32_t)Q, (uint32_t)R, ga_dev ? 1u : 0u};
-    dev_absorb_words(ctx, "zkrelu", hw, 4);
+    zk_absorb_words(ctx, "zkrelu", hw, 4);
     uint32_t hdr[8] = {ZKRL_MAGIC, hw[0], hw[1], hw[2], hw[3], 0, 0, 0};
     zk_write_proof_words(ctx, hdr, 8);
     return zk_zkrelu(ctx, z_dev, ga_dev, D, Q, R);
@@ -833,7 +808,7 @@ extern "C" int zkrelu_prove(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, 
     }
     if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, zd, gd, D, Q, R);
     int ids[4] = {0, 1, 2, 3};
-    int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, ids, 4, claims);
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 4, claims);
     zk_free(ctx, zs);
     zk_free(ctx, gs);
     return rc != ZKDL_OK ? rc : rc2;
@@ -847,7 +822,7 @@ extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_t
     int rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
     uint32_t hw[6] = {w->L, w->B, w->width, w->T, w->Q, w->R};
-    dev_absorb_words(ctx, "aggregate", hw, 6);
+    zk_absorb_words(ctx, "aggregate", hw, 6);
     uint32_t hdr[8] = {ZKAG_MAGIC, w->L, w->B, w->width, w->T, w->Q, w->R, 0};
     zk_write_proof_words(ctx, hdr, 8);
     uint64_t sa[3] = {N, w->B, w->width}, sw[3] = {N, w->width, w->width};
@@ -861,6 +836,6 @@ extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_t
     // gradW: G_W^(l) = A^(l-1)T G_Z^(l)
     if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tA, &tG, 1, 0, 0, 16, nullptr);
     if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, w->Zr, w->GA, N * w->B * w->width, (int)w->Q, (int)w->R);
-    int rc2 = call_end(ctx, tr, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
     return rc != ZKDL_OK ? rc : rc2;
 }

@@ -139,6 +139,109 @@ int zk_build_beta(zkdl_ctx* ctx, const Fr* point, int m, FrTab out) {
     return rc;
 }
 
+// ---- several tables at once: one launch for all doubling builds, one for all outer products ----
+constexpr int BETA_MAX_SMALL = 16;
+constexpr int BETA_MAX_OUTER = 8;
+
+struct BetaSmallBatch {
+    const Fr* point[BETA_MAX_SMALL];
+    int m[BETA_MAX_SMALL];
+    FrTab out[BETA_MAX_SMALL];
+};
+
+__global__ __launch_bounds__(ZK_BLOCK) void k_beta_small_batch(BetaSmallBatch bb) {
+    const Fr* point = bb.point[blockIdx.x];
+    const int m = bb.m[blockIdx.x];
+    const FrTab out = bb.out[blockIdx.x];
+    if (threadIdx.x == 0) tab_st(out, 0, fr_one());
+    __syncthreads();
+    uint64_t size = 1;
+    for (int k = m - 1; k >= 0; --k) {
+        Fr u = point[k];
+        for (uint64_t b = threadIdx.x; b < size; b += blockDim.x) {
+            Fr e = tab_ld(out, b);
+            Fr hi = fr_mul(e, u);
+            tab_st(out, b + size, hi);
+            tab_st(out, b, fr_sub(e, hi));
+        }
+        size <<= 1;
+        __syncthreads();
+    }
+}
+
+struct BetaOuterBatch {
+    FrTab hi[BETA_MAX_OUTER], lo[BETA_MAX_OUTER], out[BETA_MAX_OUTER];
+    int lo_bits[BETA_MAX_OUTER];
+    uint64_t n[BETA_MAX_OUTER];
+};
+
+__global__ __launch_bounds__(ZK_BLOCK) void k_beta_outer_batch(BetaOuterBatch ob) {
+    const int q = blockIdx.y;
+    const FrTab hi = ob.hi[q], lo = ob.lo[q], out = ob.out[q];
+    const int lo_bits = ob.lo_bits[q];
+    const uint64_t n = ob.n[q], mask = ((uint64_t)1 << lo_bits) - 1;
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n;
+         i += (uint64_t)gridDim.x * blockDim.x)
+        tab_st(out, i, fr_mul(tab_ld(hi, i >> lo_bits), tab_ld(lo, i & mask)));
+}
+
+int zk_build_beta_many(zkdl_ctx* ctx, const BetaJob* jobs, int n) {
+    BetaSmallBatch sb;
+    BetaOuterBatch ob;
+    int ns = 0, no = 0;
+    uint64_t tmp_elems = 0, max_n = 0;
+    for (int i = 0; i < n; ++i) {
+        const int m = jobs[i].m;
+        if (m > BETA_SMALL_MAX && m <= 2 * BETA_SMALL_MAX) tmp_elems += ((uint64_t)1 << (m / 2)) + ((uint64_t)1 << (m - m / 2));
+    }
+    void* tmp = tmp_elems ? zk_alloc(ctx, tmp_elems * 32) : nullptr;
+    if (tmp_elems && !tmp) return ZKDL_ENOMEM;
+    uint32_t* tp = (uint32_t*)tmp;
+    int rc = ZKDL_OK;
+    for (int i = 0; i < n && rc == ZKDL_OK; ++i) {
+        const int m = jobs[i].m;
+        const bool split = m > BETA_SMALL_MAX && m <= 2 * BETA_SMALL_MAX;
+        if (m > 2 * BETA_SMALL_MAX || ns + (split ? 2 : 1) > BETA_MAX_SMALL || (split && no + 1 > BETA_MAX_OUTER)) {
+            rc = zk_build_beta(ctx, jobs[i].point, m, jobs[i].out);   // large or surplus tables: one by one
+            continue;
+        }
+        if (!split) {
+            sb.point[ns] = jobs[i].point;
+            sb.m[ns] = m;
+            sb.out[ns] = jobs[i].out;
+            ++ns;
+            continue;
+        }
+        const int hb = m / 2, lb = m - hb;
+        const uint64_t hn = (uint64_t)1 << hb, ln = (uint64_t)1 << lb;
+        const FrTab th = make_tab(tp, hn);
+        tp += 8 * hn;
+        const FrTab tl = make_tab(tp, ln);
+        tp += 8 * ln;
+        sb.point[ns] = jobs[i].point;
+        sb.m[ns] = hb;
+        sb.out[ns] = th;
+        ++ns;
+        sb.point[ns] = jobs[i].point + hb;
+        sb.m[ns] = lb;
+        sb.out[ns] = tl;
+        ++ns;
+        ob.hi[no] = th;
+        ob.lo[no] = tl;
+        ob.out[no] = jobs[i].out;
+        ob.lo_bits[no] = lb;
+        ob.n[no] = (uint64_t)1 << m;
+        if (ob.n[no] > max_n) max_n = ob.n[no];
+        ++no;
+    }
+    if (rc == ZKDL_OK && ns > 0)
+        hipLaunchKernelGGL(k_beta_small_batch, dim3(ns), dim3(ZK_BLOCK), 0, ctx->stream, sb);
+    if (rc == ZKDL_OK && no > 0)
+        hipLaunchKernelGGL(k_beta_outer_batch, dim3(grid_for(max_n, 4096), no), dim3(ZK_BLOCK), 0, ctx->stream, ob);
+    zk_free(ctx, tmp);   // stream-ordered reuse
+    return rc;
+}
+
 // ---------------------------------------------------------------------------
 // partial evaluation: out[o, i] = sum_a beta[a] * T[o, a, i]
 // ---------------------------------------------------------------------------

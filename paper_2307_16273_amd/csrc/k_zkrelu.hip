@@ -1063,16 +1063,23 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     ZkBeta8 beta8;
     for (int k = 0; k < 5; ++k) beta8.t[k] = make_tab((uint32_t*)beta_mem + (uint64_t)k * 8 * D, D);
 
-    int rc = zk_build_beta(ctx, st->chal + c_uz, li, beta8.t[0]);
-    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ua, li, beta8.t[1]);
-    if (rc == ZKDL_OK && has_ga) rc = zk_build_beta(ctx, st->chal + c_uga, li, beta8.t[2]);
-    if (rc == ZKDL_OK && has_ga) rc = zk_build_beta(ctx, st->chal + c_ugz, li, beta8.t[3]);
-    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ubin, li, beta8.t[4]);
     // beta_J as an array of structures: one plane of J elements read through FrTab, then copied
     void* bj_tmp = zk_alloc(ctx, 64 * 32);
-    if (!bj_tmp) rc = ZKDL_ENOMEM;
+    int rc = bj_tmp ? ZKDL_OK : ZKDL_ENOMEM;
     FrTab bj_soa = make_tab(bj_tmp, J);
-    if (rc == ZKDL_OK) rc = zk_build_beta(ctx, st->chal + c_ubin + li, lj, bj_soa);
+    if (rc == ZKDL_OK) {
+        BetaJob jobs[6];
+        int nj = 0;
+        jobs[nj++] = BetaJob{st->chal + c_uz, li, beta8.t[0]};
+        jobs[nj++] = BetaJob{st->chal + c_ua, li, beta8.t[1]};
+        if (has_ga) {
+            jobs[nj++] = BetaJob{st->chal + c_uga, li, beta8.t[2]};
+            jobs[nj++] = BetaJob{st->chal + c_ugz, li, beta8.t[3]};
+        }
+        jobs[nj++] = BetaJob{st->chal + c_ubin, li, beta8.t[4]};
+        jobs[nj++] = BetaJob{st->chal + c_ubin + li, lj, bj_soa};
+        rc = zk_build_beta_many(ctx, jobs, nj);
+    }
     if (rc != ZKDL_OK) {
         zk_free(ctx, bj_tmp);
         zk_free(ctx, mem);

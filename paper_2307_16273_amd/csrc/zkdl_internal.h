@@ -15,6 +15,7 @@ constexpr int ZK_PROOF_CAP = 1 << 17;      // proof bytes one call may write
 constexpr int ZK_MAX_PART_BLOCKS = 1024;   // partial-sum slots of a round kernel
 constexpr int ZK_MAX_EVALS = 4;            // evaluations per round polynomial (degree <= 3)
 constexpr int ZK_BLOCK = 256;
+constexpr int ZK_PEND_CAP = 512;         // host-known transcript frames waiting for the next transcript kernel
 
 // Device-resident state of the call in flight.
 struct DevState {
@@ -58,6 +59,10 @@ struct zkdl_ctx {
     // per-call bookkeeping (host mirrors of device cursors)
     int n_chal;
     size_t proof_len;
+    // transcript frames known on the host (protocol headers) that the next transcript
+    // kernel absorbs before anything else; whole 64-byte blocks
+    uint8_t pend[ZK_PEND_CAP];
+    uint32_t pend_len;
     // optional per-kernel-class timing with HIP events on the context's stream
     bool prof_on;
     struct ProfSpan {
@@ -106,6 +111,13 @@ void zk_launch_download(zkdl_ctx* ctx, FrTab in, uint64_t n, uint8_t* out_le_dev
 void zk_launch_points_to_mont(zkdl_ctx* ctx, const uint8_t* le_dev, int n, Fr* out);
 // beta~(point, .) for the m challenges point[0..m) (device, Montgomery, AoS)
 int zk_build_beta(zkdl_ctx* ctx, const Fr* point, int m, FrTab out);
+// several tables with two launches in all (tables of more than 2^22 entries are built one by one)
+struct BetaJob {
+    const Fr* point;   // device, Montgomery form, m coordinates
+    int m;
+    FrTab out;         // 2^m entries
+};
+int zk_build_beta_many(zkdl_ctx* ctx, const BetaJob* jobs, int n);
 // out[o, i] = sum_a beta[a] * src[o, a, i]; src kind TK_*; out has O * I elements
 int zk_partial_eval(zkdl_ctx* ctx, int kind, const void* src, uint64_t O, uint64_t A, uint64_t I,
                     FrTab beta, FrTab out);
@@ -121,7 +133,12 @@ void zk_launch_shift_rows(zkdl_ctx* ctx, FrTab src, uint64_t rows, uint64_t inne
 size_t zk_sumcheck_work_bytes(int K, int d);
 int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, void* work_mem, int d,
                         int finals_scal_base);
+// Queues the frame of a protocol header (label, n <= 8 little-endian u32 words); it is absorbed
+// by the next zk_launch_draw / zk_flush_frames, in stream order before everything that follows.
+void zk_absorb_words(zkdl_ctx* ctx, const char* label, const uint32_t* words, int n);
+// absorbs the queued frames, then draws `count` challenges into chal[chal_base ..)
 void zk_launch_draw(zkdl_ctx* ctx, int chal_base, int count);
+static inline void zk_flush_frames(zkdl_ctx* ctx) { zk_launch_draw(ctx, 0, 0); }
 
 // ---- k_zkrelu.hip ----------------------------------------------------------------
 int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q, int R);
