@@ -203,9 +203,9 @@ __device__ __forceinline__ void line3(const F9& lo, const F9& hi, F9 e[3]) {
 
 // Linear equations of one i-round: sum over i' of
 //   (r^2 beta_Z) Z + (r beta_A)(1 - sign) Z' + (r'r^2 beta_GA) G_A + (r'r beta_GZ)(1 - sign) G_A'
-// at x = 0, 2, 3 (x = 1 comes from the claim); beta_I is folded along for the binarity kernels.
+// at x = 0, 2, 3 (x = 1 comes from the claim).
 template <bool FOLD>
-__global__ __launch_bounds__(ZK_BLOCK) void k_zk_lin(LinArgs a) {
+__device__ __forceinline__ void lin_body(const LinArgs& a, const unsigned bx, const unsigned gx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     F9 acc[3];
 #pragma unroll
@@ -213,12 +213,11 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_lin(LinArgs a) {
     F9 v = f9_zero();
     if (FOLD) v = fr_unpack(*a.chal);
     const uint64_t m = a.m;
-    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
-         b += (uint64_t)gridDim.x * blockDim.x) {
+    for (uint64_t b = bx * (uint64_t)blockDim.x + threadIdx.x; b < m;
+         b += (uint64_t)gx * blockDim.x) {
         F9 lo, hi, ns[3], p[3], q[3];
         lin_pair<FOLD>(a.tabs.t[T_NS], b, m, v, lo, hi);
         line3<false>(lo, hi, ns);
-        lin_pair<FOLD>(a.tabs.t[T_BI], b, m, v, lo, hi);
         lin_pair<FOLD>(a.tabs.t[T_BZ], b, m, v, lo, hi);
         line3<true>(lo, hi, p);
         lin_pair<FOLD>(a.tabs.t[T_Z], b, m, v, lo, hi);
@@ -252,7 +251,7 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_lin(LinArgs a) {
     }
     {   // thread j holds the sum for x = 0, 2, 3; g(1) is derived from the claim
         const Fr s = block_sum_lazy<3>(acc, red);
-        Fr* pp = a.part + (uint64_t)blockIdx.x * 4;
+        Fr* pp = a.part + (uint64_t)bx * 4;
         if (threadIdx.x < 3) pp[threadIdx.x ? threadIdx.x + 1 : 0] = s;
         else if (threadIdx.x == 3) pp[1] = fr_zero();
     }
@@ -271,7 +270,10 @@ struct BinArgs {
     uint64_t m;            // pairs this round
     int jc;                // columns per thread
     const Fr* chal;
-    F9Tab bI;              // beta_I, lazy limbs (folded by the linear kernel of the same round)
+    F9Tab bI;              // beta_I, lazy limbs: round 0 the table as built; later the entries for
+                           // both values of the previous variable (length 4m)
+    F9Tab bI_out;          // rounds >= 1: receives the pair folded with vprev (length 2m)
+    const Fr* vprev;       // rounds >= 1: challenge of the previous round
     const Fr* bJ;          // J entries
     const Fr* rp;          // r'
     Fr* part;              // partials of this kernel
@@ -295,7 +297,7 @@ __device__ __forceinline__ Fr masked_sum(const Fr* bJ, uint64_t mask, int nbits)
 // Round 0: both halves are bits, a(x)^2 - a(x) = (x^2 - x) [lo != hi]; contributes
 // 2 beta_I(2, i') C(i') at x = 2 and 6 beta_I(3, i') C(i') at x = 3,
 // C = sum_j beta_J(j) ([z bits differ] + r' [g bits differ]).
-__global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin0(BinArgs a) {
+__device__ __forceinline__ void bin0_body(const BinArgs& a, const unsigned bx, const unsigned gx) {
     __shared__ uint32_t red[64];
     __shared__ Fr sbj[64];
     if (threadIdx.x < 64) sbj[threadIdx.x] = threadIdx.x < (unsigned)a.nbits ? a.bJ[threadIdx.x] : fr_zero();
@@ -304,8 +306,8 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin0(BinArgs a) {
     const uint64_t m = a.m;
     const uint64_t keep = a.nbits >= 64 ? ~(uint64_t)0 : (((uint64_t)1 << a.nbits) - 1);
     Fr rp = *a.rp;
-    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
-         b += (uint64_t)gridDim.x * blockDim.x) {
+    for (uint64_t b = bx * (uint64_t)blockDim.x + threadIdx.x; b < m;
+         b += (uint64_t)gx * blockDim.x) {
         uint64_t dz = ((uint64_t)a.z[b] ^ (uint64_t)a.z[b + m]) & keep;
         Fr c = masked_sum(sbj, dz, a.nbits);
         if (a.has_ga) {
@@ -324,7 +326,7 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin0(BinArgs a) {
     Fr s2 = block_sum(acc2, red);
     Fr s3 = block_sum(acc3, red);
     if (threadIdx.x == 0) {
-        Fr* p = a.part + (uint64_t)blockIdx.x * 4;
+        Fr* p = a.part + (uint64_t)bx * 4;
         p[0] = fr_zero();
         p[1] = fr_zero();
         p[2] = s2;
@@ -371,10 +373,17 @@ __device__ __forceinline__ F9 masked_sum9(const F9* sbj, uint64_t mask) {
     return f9_norm(s);
 }
 
-// beta_I(x, i') at x = 0, 2, 3 from the pair (lo, hi) of the packed table; all normal
-__device__ __forceinline__ void beta_line(const F9Tab& bI, uint64_t b, uint64_t m, F9 e[3]) {
-    F9 lo = f9tab_ld(bI, b), hi = f9tab_ld(bI, b + m);
-    F9 dn = f9_norm(f9_sub(hi, lo));
+// beta_I in rounds t >= 1: the source still has the entries for both values of the previous
+// variable (length 4m); bind the previous challenge, leave the folded pair in the other buffer
+// for the next round (every column chunk writes the same values), return the line at 0, 2, 3
+__device__ __forceinline__ void beta_line_fold(const BinArgs& a, uint64_t b, uint64_t m, const F9& vprev, F9 e[3]) {
+    const F9 t0 = f9tab_ld(a.bI, b), t1 = f9tab_ld(a.bI, b + m);
+    const F9 t2 = f9tab_ld(a.bI, b + 2 * m), t3 = f9tab_ld(a.bI, b + 3 * m);
+    const F9 lo = f9_norm_reduce(f9_add(t0, f9_mul(f9_sub(t2, t0), vprev)));
+    const F9 hi = f9_norm_reduce(f9_add(t1, f9_mul(f9_sub(t3, t1), vprev)));
+    f9tab_st(a.bI_out, b, lo);
+    f9tab_st(a.bI_out, b + m, hi);
+    const F9 dn = f9_norm(f9_sub(hi, lo));
     e[0] = lo;
     e[1] = f9_norm(f9_add(hi, dn));
     e[2] = f9_norm(f9_add(e[1], dn));
@@ -382,7 +391,7 @@ __device__ __forceinline__ void beta_line(const F9Tab& bI, uint64_t b, uint64_t 
 
 // Round 1 by look-up.  m = D/4 quadruples (i'', i''+m | i''+2m, i''+3m) = (x0, x1) in
 // {(0,0), (0,1), (1,0), (1,1)}.  Writes partial sums for x = 0, 2, 3 (x = 1 comes from the claim).
-__global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin1(BinArgs a) {
+__device__ __forceinline__ void bin1_body(const BinArgs& a, const unsigned bx, const unsigned gx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ F9 sbj[64];
     __shared__ F9 qx[2][3][16];   // [slice][x in {0,2,3}][combination]; slice 1 carries r'
@@ -402,11 +411,12 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin1(BinArgs a) {
     }
     __syncthreads();
     const uint64_t m = a.m;
+    const F9 vprev9 = fr_unpack(*a.vprev);
     const uint64_t keep = a.nbits >= 64 ? ~(uint64_t)0 : (((uint64_t)1 << a.nbits) - 1);
     F9 tot[3];
 #pragma unroll
     for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
-    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+    for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
         F9 acc[3];
 #pragma unroll
         for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
@@ -435,14 +445,14 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin1(BinArgs a) {
             }
         }
         F9 bi[3];
-        beta_line(a.bI, b, m, bi);
+        beta_line_fold(a, b, m, vprev9, bi);
 #pragma unroll
         for (int x = 0; x < 3; ++x)
             tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_norm_reduce(acc[x]))));
     }
     {
         const Fr s = block_sum_lazy<3>(tot, red);
-        Fr* p = a.part + (uint64_t)blockIdx.x * 4;
+        Fr* p = a.part + (uint64_t)bx * 4;
         if (tid < 3) p[tid ? tid + 1 : 0] = s;
         else if (tid == 3) p[1] = fr_zero();
     }
@@ -504,7 +514,7 @@ __device__ __forceinline__ void bound2_values(const Fr* chal, F9* val16) {
     }
 }
 
-__global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin2(BinArgs a) {
+__device__ __forceinline__ void bin2_body(const BinArgs& a, const unsigned bx, const unsigned by, const unsigned gx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ F9 sbj[2][64];
     __shared__ F9 val16[16];
@@ -535,12 +545,13 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin2(BinArgs a) {
     }
     __syncthreads();
     const uint64_t m = a.m;
-    int j0 = blockIdx.y * a.jc, j1 = j0 + a.jc;
+    const F9 vprev9 = fr_unpack(*a.vprev);
+    int j0 = by * a.jc, j1 = j0 + a.jc;
     if (j1 > a.nbits) j1 = a.nbits;
     F9 tot[3];
 #pragma unroll
     for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
-    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+    for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
         uint64_t cols[3][17];
 #pragma unroll
         for (int x = 0; x < 3; ++x)
@@ -572,14 +583,14 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_bin2(BinArgs a) {
             }
         }
         F9 bi[3];
-        beta_line(a.bI, b, m, bi);
+        beta_line_fold(a, b, m, vprev9, bi);
 #pragma unroll
         for (int x = 0; x < 3; ++x) {
             f9_cols_norm<17>(cols[x]);
             tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_redc(cols[x]))));
         }
     }
-    const uint64_t blk = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    const uint64_t blk = (uint64_t)by * gx + bx;
     {
         const Fr s = block_sum_lazy<3>(tot, red);
         Fr* p = a.part + blk * 4;
@@ -631,7 +642,7 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat3(BinArgs a) {
 // first when FOLD; q(x) = e(x) (e(x) - 1) at x = 0, 2, 3; per thread the sum over its columns
 // of beta_J(j) q(x) (slice 1 with r' beta_J), then times beta_I(x, i').
 template <bool FOLD>
-__global__ __launch_bounds__(ZK_BLOCK) void k_zk_binl(BinArgs a) {
+__device__ __forceinline__ void binl_body(const BinArgs& a, const unsigned bx, const unsigned by, const unsigned gx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ F9 sbj[2][64];
     const int tid = threadIdx.x;
@@ -643,15 +654,16 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_binl(BinArgs a) {
     }
     __syncthreads();
     const uint64_t m = a.m;
+    const F9 vprev9 = fr_unpack(*a.vprev);
     F9 v = f9_zero();
     if (FOLD) v = fr_unpack(*a.chal);
     const F9 one9 = fr_unpack(fr_one());
-    int j0 = blockIdx.y * a.jc, j1 = j0 + a.jc;
+    int j0 = by * a.jc, j1 = j0 + a.jc;
     if (j1 > a.nbits) j1 = a.nbits;
     F9 tot[3];
 #pragma unroll
     for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
-    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+    for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
         // sum over the columns of beta_J(j) q(x) as 64-bit columns: one reduction per (i', x)
         uint64_t cols[3][17];
 #pragma unroll
@@ -694,7 +706,7 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_binl(BinArgs a) {
             }
         }
         F9 bi[3];
-        beta_line(a.bI, b, m, bi);
+        beta_line_fold(a, b, m, vprev9, bi);
 #pragma unroll
         for (int x = 0; x < 3; ++x) {
             // at most 128 products below 2 r^2 each: the reduced sum is below 4.8 r, normal
@@ -702,13 +714,43 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_binl(BinArgs a) {
             tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_redc(cols[x]))));
         }
     }
-    const uint64_t blk = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    const uint64_t blk = (uint64_t)by * gx + bx;
     {
         const Fr s = block_sum_lazy<3>(tot, red);
         Fr* p = a.part + blk * 4;
         if (tid < 3) p[tid ? tid + 1 : 0] = s;
         else if (tid == 3) p[1] = fr_zero();
     }
+}
+
+// One launch per i-round: the first nb_lin blocks take the linear equations, the others the
+// binarity terms (column chunk = block / bin_gx).  The two parts share no table, so they run
+// side by side; their partial sums land in one array that the round's finaliser adds up.
+struct ZkRoundArgs {
+    LinArgs lin;
+    BinArgs bin;
+    unsigned nb_lin, bin_gx;
+};
+
+// MODE 0: first round; 1, 2: look-up rounds on the integers; 3: first round on the columns
+// in memory; 4: later rounds (fold the columns with the previous challenge first)
+template <int MODE>
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_round(ZkRoundArgs a) {
+    if (blockIdx.x < a.nb_lin) {
+        lin_body<MODE != 0>(a.lin, blockIdx.x, a.nb_lin);
+        return;
+    }
+    const unsigned bid = blockIdx.x - a.nb_lin;
+    const unsigned bx = bid % a.bin_gx, by = bid / a.bin_gx;
+    if (MODE == 0) bin0_body(a.bin, bx, a.bin_gx);
+    else if (MODE == 1) bin1_body(a.bin, bx, a.bin_gx);
+    else if (MODE == 2) bin2_body(a.bin, bx, by, a.bin_gx);
+    else binl_body<MODE == 4>(a.bin, bx, by, a.bin_gx);
+}
+
+template <int MODE>
+static void launch_zk_round(zkdl_ctx* ctx, const ZkRoundArgs& ra, unsigned nb_bin) {
+    hipLaunchKernelGGL((k_zk_round<MODE>), dim3(ra.nb_lin + nb_bin), dim3(ZK_BLOCK), 0, ctx->stream, ra);
 }
 
 // ---------------------------------------------------------------------------
@@ -1043,7 +1085,8 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     const int mat_bound = li >= 3 ? 3 : 2;
     const uint64_t rows = li >= 3 ? D / 8 : 1;
     const uint64_t aux_elems = (uint64_t)(has_ga ? 2 : 1) * nbits * rows;
-    void* mem = zk_alloc(ctx, (uint64_t)LIN_TABLES * D * 36 + 64 * 32 + (li >= 2 ? aux_elems * 36 : 0));
+    const uint64_t alt_rows = D >= 2 ? D / 2 : 1;   // second buffer of the beta_I folds
+    void* mem = zk_alloc(ctx, (uint64_t)LIN_TABLES * D * 36 + 64 * 32 + alt_rows * 36 + (li >= 2 ? aux_elems * 36 : 0));
     void* beta_mem = zk_alloc(ctx, (uint64_t)5 * D * 32);
     if (!mem || !beta_mem) {
         zk_free(ctx, mem);
@@ -1059,6 +1102,10 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     }
     Fr* bJ = (Fr*)base;
     base += 8 * 64;
+    F9Tab bI_alt;
+    bI_alt.p = base;
+    bI_alt.ps = alt_rows;
+    base += 9 * alt_rows;
     uint32_t* aux = base;
     ZkBeta8 beta8;
     for (int k = 0; k < 5; ++k) beta8.t[k] = make_tab((uint32_t*)beta_mem + (uint64_t)k * 8 * D, D);
@@ -1119,6 +1166,8 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     ba.nbits = nbits;
     ba.has_ga = has_ga;
     ba.bI = tabs.t[T_BI];
+    ba.bI_out = bI_alt;
+    ba.vprev = nullptr;
     ba.bJ = bJ;
     ba.rp = &st->weights[4];
     ba.jc = nbits;
@@ -1128,56 +1177,47 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
 
     for (int t = 0; t < li; ++t) {
         const uint64_t m = D >> (t + 1);
-        LinArgs la;
-        la.tabs = tabs;
-        la.m = m;
-        la.chal = t > 0 ? &st->chal[c_v + t - 1] : nullptr;
-        la.part = ctx->partials;
-        la.has_ga = has_ga;
-        unsigned nb_lin = blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
-        const double n_lin = has_ga ? 10.0 : 6.0;
-        zk_prof_begin(ctx, ZKDL_PROF_ZK_LIN, n_lin * (t == 0 ? 64.0 : 192.0) * (double)m);
-        if (t == 0) hipLaunchKernelGGL(k_zk_lin<false>, dim3(nb_lin), dim3(ZK_BLOCK), 0, ctx->stream, la);
-        else hipLaunchKernelGGL(k_zk_lin<true>, dim3(nb_lin), dim3(ZK_BLOCK), 0, ctx->stream, la);
-        zk_prof_end(ctx);
+        ZkRoundArgs ra;
+        ra.lin.tabs = tabs;
+        ra.lin.m = m;
+        ra.lin.chal = t > 0 ? &st->chal[c_v + t - 1] : nullptr;
+        ra.lin.part = ctx->partials;
+        ra.lin.has_ga = has_ga;
+        const unsigned nb_lin = blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
+        ra.nb_lin = nb_lin;
+        // beta_I: round 0 reads the table as built; round t >= 1 reads what round t-1 left (the
+        // table as built for t = 1), binds v_{t-1} and leaves the folded pair in the other buffer
+        ba.bI = (t == 0 || (t & 1)) ? tabs.t[T_BI] : bI_alt;
+        ba.bI_out = (t & 1) ? bI_alt : tabs.t[T_BI];
+        ba.vprev = t > 0 ? &st->chal[c_v + t - 1] : nullptr;
         ba.m = m;
         ba.part = ctx->partials + (uint64_t)nb_lin * 4;
-        unsigned nb_bin;
-        if (t == 0) {
-            nb_bin = blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
-            zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, (has_ga ? 32.0 : 16.0) * (double)m + 64.0 * (double)m);
-            hipLaunchKernelGGL(k_zk_bin0, dim3(nb_bin), dim3(ZK_BLOCK), 0, ctx->stream, ba);
-            zk_prof_end(ctx);
-        } else if (t == 1) {
-            // second round: look-up on the integers, nothing in memory yet
-            nb_bin = blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
-            ba.chal = &st->chal[c_v];
-            zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, (has_ga ? 64.0 : 32.0) * (double)m + 64.0 * (double)m);
-            hipLaunchKernelGGL(k_zk_bin1, dim3(nb_bin), dim3(ZK_BLOCK), 0, ctx->stream, ba);
-            zk_prof_end(ctx);
-        } else {
-            // few rows: split the columns over more threads
-            int jc = nbits;
+        // few rows: split the columns over more blocks (rounds on the 64-bit words take them whole)
+        int jc = nbits;
+        if (t >= 2)
             while ((uint64_t)((nbits + jc - 1) / jc) * m < 32768 && jc > 1) jc = (jc + 1) / 2;
-            unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
-            unsigned bx = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / chunks);
-            ba.jc = jc;
-            if (t == 2) {
-                // third round: look-up again, on the eight rows of a pair index
-                ba.chal = &st->chal[c_v];
-                zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, (has_ga ? 128.0 : 64.0) * (double)m + 64.0 * (double)m);
-                hipLaunchKernelGGL(k_zk_bin2, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
-                zk_prof_end(ctx);
-            } else {
-                ba.chal = t >= 4 ? &st->chal[c_v + t - 1] : nullptr;
-                zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN,
-                              (has_ga ? 2.0 : 1.0) * nbits * (t >= 4 ? 216.0 : 72.0) * (double)m + 64.0 * (double)m);
-                if (t >= 4) hipLaunchKernelGGL(k_zk_binl<true>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
-                else hipLaunchKernelGGL(k_zk_binl<false>, dim3(bx, chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
-                zk_prof_end(ctx);
-            }
-            nb_bin = bx * chunks;
-        }
+        const unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
+        const unsigned bx = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / chunks);
+        const unsigned nb_bin = bx * chunks;
+        ba.jc = jc;
+        ba.chal = t == 0 ? nullptr : t <= 2 ? &st->chal[c_v] : t >= 4 ? &st->chal[c_v + t - 1] : nullptr;
+        ra.bin = ba;
+        ra.bin_gx = bx;
+        // algorithmic bytes: the linear tables (9 of them with G_A, 5 without) and beta_I in 36-byte
+        // entries, the integers or the columns of the binarity part
+        const double n_lin = has_ga ? 9.0 : 5.0, ns = has_ga ? 2.0 : 1.0;
+        double bytes = n_lin * (t == 0 ? 72.0 : 216.0) * (double)m + (t == 0 ? 72.0 : 216.0) * (double)m;
+        if (t == 0) bytes += ns * 16.0 * (double)m;
+        else if (t == 1) bytes += ns * 32.0 * (double)m;
+        else if (t == 2) bytes += ns * 64.0 * (double)m;
+        else bytes += ns * nbits * (t >= 4 ? 216.0 : 72.0) * (double)m;
+        zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, bytes);
+        if (t == 0) launch_zk_round<0>(ctx, ra, nb_bin);
+        else if (t == 1) launch_zk_round<1>(ctx, ra, nb_bin);
+        else if (t == 2) launch_zk_round<2>(ctx, ra, nb_bin);
+        else if (t == 3) launch_zk_round<3>(ctx, ra, nb_bin);
+        else launch_zk_round<4>(ctx, ra, nb_bin);
+        zk_prof_end(ctx);
         // g(1) is taken from the running claim: the binarity kernels leave it out
         zk_launch_finalise(ctx, (int)(nb_lin + nb_bin), 4, c_v + t, rounds_off + (uint32_t)t * 128, 0, 0, 1);
         if (t + 1 == mat_bound) {
@@ -1196,6 +1236,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     }
     TailArgs ta;
     ta.tabs = tabs;
+    if (li >= 2 && ((li - 1) & 1)) ta.tabs.t[T_BI] = bI_alt;   // where the last round left beta_I
     ta.bin = ba;
     ta.li = li;
     ta.lj = lj;
