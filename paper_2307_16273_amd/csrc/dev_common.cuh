@@ -47,6 +47,19 @@ __device__ __forceinline__ Fr block_sum(Fr x, uint32_t* red) {
 // below 64 * 2.41 r < 2^263); at most 8 such wave sums are added before the final reduction.
 // red: BLOCK_SUM_LAZY_WORDS words of LDS.
 constexpr int BLOCK_SUM_LAZY_WORDS = 8 * ZK_MAX_EVALS * 9;
+
+// Sum over the 64 lanes of a wave of a lazy value (normal limbs, below 2.41 r); every lane
+// must call; lane 0 returns the total, normal and below 2.41 r.
+__device__ __forceinline__ F9 wave_sum_lazy(F9 s) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+        for (int l = 0; l < 9; ++l) s.v[l] += __shfl_down(s.v[l], off, 64);
+        if (off == 8) s = f9_norm(s);
+    }
+    return f9_norm_reduce(s);
+}
+
 template <int N>
 __device__ __forceinline__ Fr block_sum_lazy(const F9 (&x)[N], uint32_t* red) {
     static_assert(N <= ZK_MAX_EVALS, "red is sized for ZK_MAX_EVALS values");
@@ -54,26 +67,13 @@ __device__ __forceinline__ Fr block_sum_lazy(const F9 (&x)[N], uint32_t* red) {
     const int n_waves = (blockDim.x + 63) >> 6;
     F9 s[N];
 #pragma unroll
-    for (int j = 0; j < N; ++j) s[j] = x[j];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-#pragma unroll
-        for (int j = 0; j < N; ++j)
-#pragma unroll
-            for (int l = 0; l < 9; ++l) s[j].v[l] += __shfl_down(s[j].v[l], off, 64);
-        if (off == 8) {
-#pragma unroll
-            for (int j = 0; j < N; ++j) s[j] = f9_norm(s[j]);
-        }
-    }
+    for (int j = 0; j < N; ++j) s[j] = wave_sum_lazy(x[j]);
     __syncthreads();   // red may still be read from a previous call
     if (lane == 0) {
 #pragma unroll
-        for (int j = 0; j < N; ++j) {
-            const F9 r = f9_norm_reduce(s[j]);
+        for (int j = 0; j < N; ++j)
 #pragma unroll
-            for (int l = 0; l < 9; ++l) red[(wave * N + j) * 9 + l] = r.v[l];
-        }
+            for (int l = 0; l < 9; ++l) red[(wave * N + j) * 9 + l] = s[j].v[l];
     }
     __syncthreads();
     Fr out = fr_zero();

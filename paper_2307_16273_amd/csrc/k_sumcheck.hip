@@ -226,32 +226,90 @@ struct ScTailArgs {
 template <int K>
 __global__ __launch_bounds__(ZK_BLOCK) void k_sc_tail(ScTailArgs a) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    __shared__ uint32_t el[2][K][2][9][64];   // small rounds: [buffer][table][lo/hi][limb][pair]
     __shared__ TsShared S;
     __shared__ Fr g[ZK_MAX_EVALS + 1];
     DevState* st = a.st;
     block_ts_load(S, st);
     uint64_t m = a.ra.m;
     F9 v = fr_unpack(st->chal[a.first_chal]);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int el_cur = -1;   // buffer of `el` that holds the current tables; -1: they are in memory
     for (int t = 0; t < a.rounds; ++t) {
-        F9 acc[K + 1];
+        if (m > 64) {
+            F9 acc[K + 1];
 #pragma unroll
-        for (int x = 0; x <= K; ++x) acc[x] = f9_zero();
-        int pending = 0;
-        for (uint64_t b = threadIdx.x; b < m; b += blockDim.x) {
-            sc_pair<K, 2>(a.ra, b, m, v, acc);
-            if (++pending == 2) {
-                pending = 0;
+            for (int x = 0; x <= K; ++x) acc[x] = f9_zero();
+            int pending = 0;
+            for (uint64_t b = threadIdx.x; b < m; b += blockDim.x) {
+                sc_pair<K, 2>(a.ra, b, m, v, acc);
+                if (++pending == 2) {
+                    pending = 0;
 #pragma unroll
-                for (int x = 0; x <= K; ++x) acc[x] = f9_norm_reduce(acc[x]);
+                    for (int x = 0; x <= K; ++x) acc[x] = f9_norm_reduce(acc[x]);
+                }
             }
-        }
-        {
             F9 need[K];
 #pragma unroll
             for (int j = 0; j < K; ++j) need[j] = f9_norm_reduce(acc[j >= 1 ? j + 1 : j]);
             const Fr s = block_sum_lazy<K>(need, red);
             if (threadIdx.x < K) g[threadIdx.x >= 1 ? threadIdx.x + 1 : 0] = s;
             if (threadIdx.x == 0) g[1] = fr_sub(st->claim, s);
+        } else {
+            // At most 64 pairs: a thread per (table, pair) folds, then a thread per
+            // (evaluation point, pair) multiplies, so a round is two products deep instead of
+            // 4 K; wave w sums the point x = 0, 2, 3 [w] by itself.  The folded pairs stay in
+            // LDS from here on (stores of a few words per plane to memory are slow).
+            const int mi = (int)m;
+            const int nxt = el_cur < 0 ? 0 : el_cur ^ 1;
+            if (wave < K && lane < mi) {
+                F9 t4[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int i = lane + q * mi;   // index in the table of length 4 m
+                    if (el_cur < 0) {
+                        t4[q] = f9tab_ld(a.ra.work[wave], (uint64_t)i);
+                    } else {
+                        const int h = i >= 2 * mi, b = i - h * 2 * mi;
+#pragma unroll
+                        for (int l = 0; l < 9; ++l) t4[q].v[l] = el[el_cur][wave][h][l][b];
+                    }
+                }
+                const F9 lo = f9_norm_reduce(f9_add(t4[0], f9_mul(f9_sub(t4[2], t4[0]), v)));
+                const F9 hi = f9_norm_reduce(f9_add(t4[1], f9_mul(f9_sub(t4[3], t4[1]), v)));
+#pragma unroll
+                for (int l = 0; l < 9; ++l) {
+                    el[nxt][wave][0][l][lane] = lo.v[l];
+                    el[nxt][wave][1][l][lane] = hi.v[l];
+                }
+            }
+            __syncthreads();
+            F9 prod = f9_zero();
+            if (wave < K && lane < mi) {
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    F9 lo, hi;
+#pragma unroll
+                    for (int l = 0; l < 9; ++l) {
+                        lo.v[l] = el[nxt][k][0][l][lane];
+                        hi.v[l] = el[nxt][k][1][l][lane];
+                    }
+                    F9 e = lo;
+                    if (wave >= 1) {   // x = 2, 3: hi + (x - 1)(hi - lo); limbs below 2^30.6
+                        const F9 dn = f9_norm(f9_sub(hi, lo));
+                        e = f9_add(hi, dn);
+                        if (wave == 2) e = f9_add(e, dn);
+                        if (k == 0) e = f9_norm(e);   // the running product needs one normal factor
+                    }
+                    prod = k == 0 ? e : f9_mul(prod, e);
+                }
+                prod = f9_norm_reduce(prod);
+            }
+            const F9 s = wave_sum_lazy(prod);
+            if (wave < K && lane == 0) g[wave == 0 ? 0 : wave + 1] = f9_to_fr(s);
+            __syncthreads();
+            if (threadIdx.x == 0) g[1] = fr_sub(st->claim, g[0]);
+            el_cur = nxt;
         }
         __syncthreads();
         Fr vr = block_finalise_round(S, st, g, K + 1, a.rounds_off + (uint32_t)t * (K + 1) * 32,
@@ -264,8 +322,19 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_tail(ScTailArgs a) {
     __shared__ Fr f[4];
     if (threadIdx.x < K) {
         const int k = threadIdx.x;
-        Fr lo = f9_to_fr(f9tab_ld(a.ra.work[k], 0));
-        Fr hi = f9_to_fr(f9tab_ld(a.ra.work[k], 1));
+        F9 lo9, hi9;
+        if (el_cur < 0) {
+            lo9 = f9tab_ld(a.ra.work[k], 0);
+            hi9 = f9tab_ld(a.ra.work[k], 1);
+        } else {
+#pragma unroll
+            for (int l = 0; l < 9; ++l) {
+                lo9.v[l] = el[el_cur][k][0][l][0];
+                hi9.v[l] = el[el_cur][k][1][l][0];
+            }
+        }
+        Fr lo = f9_to_fr(lo9);
+        const Fr hi = f9_to_fr(hi9);
         lo = fr_add(lo, fr_mul_ni(fr_pack(f9_cond_sub(f9_norm_reduce(v))), fr_sub(hi, lo)));
         f[k] = lo;
         st->scal[a.scal_base + k] = lo;

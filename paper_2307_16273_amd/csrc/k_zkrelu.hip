@@ -257,6 +257,83 @@ __device__ __forceinline__ void lin_body(const LinArgs& a, const unsigned bx, co
     }
 }
 
+// The same sum for a round with few pairs, where one thread per pair would leave a chain
+// of 36 products: a block takes 16 pairs; first a thread per (table, pair) folds and leaves
+// the pair in LDS, then a thread per (evaluation point, equation, pair) multiplies, with
+// wave w summing the point x = 0, 2, 3 [w] by itself.
+constexpr int LIN_SMALL_PAIRS = 16;
+
+// value at x = 0, 2, 3 (xi = 0, 1, 2) of the line through (lo, hi); limbs below 2^30.6
+__device__ __forceinline__ F9 line_at(const F9& lo, const F9& hi, int xi) {
+    if (xi == 0) return lo;
+    const F9 dn = f9_norm(f9_sub(hi, lo));
+    F9 e = f9_add(hi, dn);
+    if (xi == 2) e = f9_add(e, dn);
+    return e;
+}
+
+template <bool FOLD>
+__device__ __forceinline__ void lin_body_small(const LinArgs& a, const unsigned bx) {
+    // tables in the order NS | BZ Z | BA ZP | BGA GA | BGZ GAP
+    __shared__ uint32_t pairs[9][2][9][LIN_SMALL_PAIRS];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int ntab = a.has_ga ? 9 : 5, nterm = a.has_ga ? 4 : 2;
+    const uint64_t m = a.m;
+    F9 v = f9_zero();
+    if (FOLD) v = fr_unpack(*a.chal);
+    {
+        const int ti = tid / LIN_SMALL_PAIRS, bl = tid % LIN_SMALL_PAIRS;
+        const uint64_t b = (uint64_t)bx * LIN_SMALL_PAIRS + bl;
+        if (ti < ntab) {
+            F9 lo = f9_zero(), hi = f9_zero();
+            if (b < m) {
+                const int which = ti == 0 ? T_NS : ti == 1 ? T_BZ : ti == 2 ? T_Z : ti == 3 ? T_BA : ti == 4 ? T_ZP
+                                : ti == 5 ? T_BGA : ti == 6 ? T_GA : ti == 7 ? T_BGZ : T_GAP;
+                lin_pair<FOLD>(a.tabs.t[which], b, m, v, lo, hi);
+            }
+#pragma unroll
+            for (int l = 0; l < 9; ++l) {
+                pairs[ti][0][l][bl] = lo.v[l];
+                pairs[ti][1][l][bl] = hi.v[l];
+            }
+        }
+    }
+    __syncthreads();
+    F9 prod = f9_zero();
+    {
+        const int term = lane / LIN_SMALL_PAIRS, bl = lane % LIN_SMALL_PAIRS;
+        const uint64_t b = (uint64_t)bx * LIN_SMALL_PAIRS + bl;
+        if (wave < 3 && term < nterm && b < m) {
+            const int tp = 1 + 2 * term, tq = 2 + 2 * term;   // beta table, value table
+            F9 lo, hi;
+#pragma unroll
+            for (int l = 0; l < 9; ++l) {
+                lo.v[l] = pairs[tp][0][l][bl];
+                hi.v[l] = pairs[tp][1][l][bl];
+            }
+            prod = f9_norm(line_at(lo, hi, wave));
+            if (term & 1) {   // the equations with (1 - sign)
+#pragma unroll
+                for (int l = 0; l < 9; ++l) {
+                    lo.v[l] = pairs[0][0][l][bl];
+                    hi.v[l] = pairs[0][1][l][bl];
+                }
+                prod = f9_mul(prod, line_at(lo, hi, wave));
+            }
+#pragma unroll
+            for (int l = 0; l < 9; ++l) {
+                lo.v[l] = pairs[tq][0][l][bl];
+                hi.v[l] = pairs[tq][1][l][bl];
+            }
+            prod = f9_norm_reduce(f9_mul(prod, line_at(lo, hi, wave)));
+        }
+    }
+    const F9 s = wave_sum_lazy(prod);
+    Fr* pp = a.part + (uint64_t)bx * 4;
+    if (wave < 3 && lane == 0) pp[wave ? wave + 1 : 0] = f9_to_fr(s);
+    else if (tid == 255) pp[1] = fr_zero();
+}
+
 // ---------------------------------------------------------------------------
 // i-rounds, binarity terms
 // ---------------------------------------------------------------------------
@@ -274,6 +351,7 @@ struct BinArgs {
                            // both values of the previous variable (length 4m)
     F9Tab bI_out;          // rounds >= 1: receives the pair folded with vprev (length 2m)
     const Fr* vprev;       // rounds >= 1: challenge of the previous round
+    int ksplit;            // column chunk = by / 2 and slice = by % 2 (few rows: more threads)
     const Fr* bJ;          // J entries
     const Fr* rp;          // r'
     Fr* part;              // partials of this kernel
@@ -546,7 +624,9 @@ __device__ __forceinline__ void bin2_body(const BinArgs& a, const unsigned bx, c
     __syncthreads();
     const uint64_t m = a.m;
     const F9 vprev9 = fr_unpack(*a.vprev);
-    int j0 = by * a.jc, j1 = j0 + a.jc;
+    const unsigned chunk = a.ksplit ? by >> 1 : by;
+    const int k0 = a.ksplit ? (int)(by & 1) : 0, k1 = a.ksplit ? k0 + 1 : (a.has_ga ? 2 : 1);
+    int j0 = chunk * a.jc, j1 = j0 + a.jc;
     if (j1 > a.nbits) j1 = a.nbits;
     F9 tot[3];
 #pragma unroll
@@ -558,7 +638,7 @@ __device__ __forceinline__ void bin2_body(const BinArgs& a, const unsigned bx, c
 #pragma unroll
             for (int c = 0; c < 17; ++c) cols[x][c] = 0;
         int pending = 0;
-        for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+        for (int k = k0; k < k1; ++k) {
             const int64_t* src = k == 0 ? a.z : a.ga;
             uint64_t w[8];
 #pragma unroll
@@ -658,7 +738,9 @@ __device__ __forceinline__ void binl_body(const BinArgs& a, const unsigned bx, c
     F9 v = f9_zero();
     if (FOLD) v = fr_unpack(*a.chal);
     const F9 one9 = fr_unpack(fr_one());
-    int j0 = by * a.jc, j1 = j0 + a.jc;
+    const unsigned chunk = a.ksplit ? by >> 1 : by;
+    const int k0 = a.ksplit ? (int)(by & 1) : 0, k1 = a.ksplit ? k0 + 1 : (a.has_ga ? 2 : 1);
+    int j0 = chunk * a.jc, j1 = j0 + a.jc;
     if (j1 > a.nbits) j1 = a.nbits;
     F9 tot[3];
 #pragma unroll
@@ -672,7 +754,7 @@ __device__ __forceinline__ void binl_body(const BinArgs& a, const unsigned bx, c
             for (int c = 0; c < 17; ++c) cols[x][c] = 0;
         int pending = 0;
         for (int j = j0; j < j1; ++j) {
-            for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+            for (int k = k0; k < k1; ++k) {
                 const F9Tab col = aux_col9(a, k, j);
                 F9 lo, hi;
                 if (FOLD) {
@@ -730,6 +812,7 @@ struct ZkRoundArgs {
     LinArgs lin;
     BinArgs bin;
     unsigned nb_lin, bin_gx;
+    int lin_small;         // the linear blocks take LIN_SMALL_PAIRS pairs each
 };
 
 // MODE 0: first round; 1, 2: look-up rounds on the integers; 3: first round on the columns
@@ -737,7 +820,8 @@ struct ZkRoundArgs {
 template <int MODE>
 __global__ __launch_bounds__(ZK_BLOCK) void k_zk_round(ZkRoundArgs a) {
     if (blockIdx.x < a.nb_lin) {
-        lin_body<MODE != 0>(a.lin, blockIdx.x, a.nb_lin);
+        if (a.lin_small) lin_body_small<MODE != 0>(a.lin, blockIdx.x);
+        else lin_body<MODE != 0>(a.lin, blockIdx.x, a.nb_lin);
         return;
     }
     const unsigned bid = blockIdx.x - a.nb_lin;
@@ -1168,6 +1252,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     ba.bI = tabs.t[T_BI];
     ba.bI_out = bI_alt;
     ba.vprev = nullptr;
+    ba.ksplit = 0;
     ba.bJ = bJ;
     ba.rp = &st->weights[4];
     ba.jc = nbits;
@@ -1183,7 +1268,10 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         ra.lin.chal = t > 0 ? &st->chal[c_v + t - 1] : nullptr;
         ra.lin.part = ctx->partials;
         ra.lin.has_ga = has_ga;
-        const unsigned nb_lin = blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
+        // few pairs: 16 per block, spread over (table, pair) and (point, equation, pair) threads
+        ra.lin_small = m <= (uint64_t)LIN_SMALL_PAIRS * (ZK_MAX_PART_BLOCKS / 2);
+        const unsigned nb_lin = ra.lin_small ? (unsigned)((m + LIN_SMALL_PAIRS - 1) / LIN_SMALL_PAIRS)
+                                             : blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
         ra.nb_lin = nb_lin;
         // beta_I: round 0 reads the table as built; round t >= 1 reads what round t-1 left (the
         // table as built for t = 1), binds v_{t-1} and leaves the folded pair in the other buffer
@@ -1196,7 +1284,10 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         int jc = nbits;
         if (t >= 2)
             while ((uint64_t)((nbits + jc - 1) / jc) * m < 32768 && jc > 1) jc = (jc + 1) / 2;
-        const unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
+        unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
+        // one column per thread already: give the two slices their own threads as well
+        ba.ksplit = (t >= 2 && has_ga && jc == 1) ? 1 : 0;
+        if (ba.ksplit) chunks *= 2;
         const unsigned bx = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / chunks);
         const unsigned nb_bin = bx * chunks;
         ba.jc = jc;
@@ -1226,6 +1317,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
             while ((uint64_t)((nbits + jc - 1) / jc) * m < 32768 && jc > 1) jc = (jc + 1) / 2;
             unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
             ba.jc = jc;
+            ba.ksplit = 0;
             ba.chal = &st->chal[c_v];
             ba.m = m;
             if (mat_bound == 2)
