@@ -383,14 +383,22 @@ __device__ inline void block_reduce_partials(const Fr* part, int nblk, int npts,
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     if (wave < npts) {
         Fr s = fr_zero();
-        int b = lane;
-        // four independent loads in flight per lane: the loop is bound by memory latency
-        for (; b + 192 < nblk; b += 256) {
-            Fr p0 = part[(uint64_t)b * npts + wave], p1 = part[(uint64_t)(b + 64) * npts + wave];
-            Fr p2 = part[(uint64_t)(b + 128) * npts + wave], p3 = part[(uint64_t)(b + 192) * npts + wave];
-            s = fr_add(fr_add(s, fr_add(p0, p1)), fr_add(p2, p3));
+        // up to eight rows of 64 partials at a time, their loads issued together: the loop is
+        // bound by memory latency
+        for (int base = 0; base < nblk; base += 512) {
+            const int rows = (nblk - base + 63) / 64 < 8 ? (nblk - base + 63) / 64 : 8;   // wave-uniform
+            Fr p[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (q < rows) {
+                    const int b = base + 64 * q + lane;
+                    p[q] = b < nblk ? part[(uint64_t)b * npts + wave] : fr_zero();
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (q < rows) s = fr_add(s, p[q]);
         }
-        for (; b < nblk; b += 64) s = fr_add(s, part[(uint64_t)b * npts + wave]);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
             Fr y;

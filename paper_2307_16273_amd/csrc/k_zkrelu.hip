@@ -818,7 +818,7 @@ struct ZkRoundArgs {
 // MODE 0: first round; 1, 2: look-up rounds on the integers; 3: first round on the columns
 // in memory; 4: later rounds (fold the columns with the previous challenge first)
 template <int MODE>
-__global__ __launch_bounds__(ZK_BLOCK) void k_zk_round(ZkRoundArgs a) {
+__global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     if (blockIdx.x < a.nb_lin) {
         if (a.lin_small) lin_body_small<MODE != 0>(a.lin, blockIdx.x);
         else lin_body<MODE != 0>(a.lin, blockIdx.x, a.nb_lin);
@@ -1283,7 +1283,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         // few rows: split the columns over more blocks (rounds on the 64-bit words take them whole)
         int jc = nbits;
         if (t >= 2)
-            while ((uint64_t)((nbits + jc - 1) / jc) * m < 32768 && jc > 1) jc = (jc + 1) / 2;
+            while ((uint64_t)((nbits + jc - 1) / jc) * m < 262144 && jc > 1) jc = (jc + 1) / 2;
         unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
         // one column per thread already: give the two slices their own threads as well
         ba.ksplit = (t >= 2 && has_ga && jc == 1) ? 1 : 0;
@@ -1314,7 +1314,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         if (t + 1 == mat_bound) {
             // bind the first challenges: bits -> field elements, one look-up per entry
             int jc = nbits;
-            while ((uint64_t)((nbits + jc - 1) / jc) * m < 32768 && jc > 1) jc = (jc + 1) / 2;
+            while ((uint64_t)((nbits + jc - 1) / jc) * m < 262144 && jc > 1) jc = (jc + 1) / 2;
             unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
             ba.jc = jc;
             ba.ksplit = 0;
