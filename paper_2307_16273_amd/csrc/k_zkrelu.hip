@@ -717,6 +717,22 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat3(BinArgs a) {
     }
 }
 
+// the raw entries of one column that a pair index needs: (b, b+m), or (b, b+m, b+2m, b+3m)
+// when the previous challenge is still to be bound
+template <bool FOLD>
+struct ColRaw {
+    F9 t[FOLD ? 4 : 2];
+};
+
+template <bool FOLD>
+__device__ __forceinline__ ColRaw<FOLD> col_load(const BinArgs& a, int k, int j, uint64_t b, uint64_t m) {
+    const F9Tab col = aux_col9(a, k, j);
+    ColRaw<FOLD> r;
+#pragma unroll
+    for (int q = 0; q < (FOLD ? 4 : 2); ++q) r.t[q] = f9tab_ld(col, b + (uint64_t)q * m);
+    return r;
+}
+
 // Rounds after the materialisation, on the columns in memory (lazy limbs, same invariants as the product
 // round kernel): per (i', j, slice) the pair (lo, hi), folded with the previous challenge
 // first when FOLD; q(x) = e(x) (e(x) - 1) at x = 0, 2, 3; per thread the sum over its columns
@@ -742,9 +758,12 @@ __device__ __forceinline__ void binl_body(const BinArgs& a, const unsigned bx, c
     const int k0 = a.ksplit ? (int)(by & 1) : 0, k1 = a.ksplit ? k0 + 1 : (a.has_ga ? 2 : 1);
     int j0 = chunk * a.jc, j1 = j0 + a.jc;
     if (j1 > a.nbits) j1 = a.nbits;
-    F9 tot[3];
+    // per-thread sums over the pair indices live in LDS: the column loop needs every register
+    __shared__ uint32_t tot_s[3][9][ZK_BLOCK];
 #pragma unroll
-    for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
+    for (int x = 0; x < 3; ++x)
+#pragma unroll
+        for (int l = 0; l < 9; ++l) tot_s[x][l][tid] = 0;
     for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
         // sum over the columns of beta_J(j) q(x) as 64-bit columns: one reduction per (i', x)
         uint64_t cols[3][17];
@@ -753,39 +772,40 @@ __device__ __forceinline__ void binl_body(const BinArgs& a, const unsigned bx, c
 #pragma unroll
             for (int c = 0; c < 17; ++c) cols[x][c] = 0;
         int pending = 0;
-        for (int j = j0; j < j1; ++j) {
-            for (int k = k0; k < k1; ++k) {
+        // the raw entries of the next column are requested before the current one is worked on
+        const int nk = k1 - k0, ncol = (j1 - j0) * nk;
+        ColRaw<FOLD> cur = col_load<FOLD>(a, k0, j0, b, m);
+        for (int c = 0; c < ncol; ++c) {
+            const int j = j0 + (nk == 2 ? c >> 1 : c), k = k0 + (nk == 2 ? (c & 1) : 0);
+            const int cn = c + 1 < ncol ? c + 1 : c;   // the last iteration asks for its own column again
+            const ColRaw<FOLD> nxt =
+                col_load<FOLD>(a, k0 + (nk == 2 ? (cn & 1) : 0), j0 + (nk == 2 ? cn >> 1 : cn), b, m);
+            F9 lo, hi;
+            if (FOLD) {
                 const F9Tab col = aux_col9(a, k, j);
-                F9 lo, hi;
-                if (FOLD) {
-                    const F9 t0 = f9tab_ld(col, b), t1 = f9tab_ld(col, b + m);
-                    const F9 t2 = f9tab_ld(col, b + 2 * m), t3 = f9tab_ld(col, b + 3 * m);
-                    lo = f9_norm_reduce(f9_add(t0, f9_mul(f9_sub(t2, t0), v)));
-                    hi = f9_norm_reduce(f9_add(t1, f9_mul(f9_sub(t3, t1), v)));
-                    f9tab_st(col, b, lo);
-                    f9tab_st(col, b + m, hi);
-                } else {
-                    lo = f9tab_ld(col, b);
-                    hi = f9tab_ld(col, b + m);
-                }
-                const F9 dn = f9_norm(f9_sub(hi, lo));
-                F9 e[3];
-                e[0] = lo;
-                e[1] = f9_norm(f9_add(hi, dn));
-                e[2] = f9_norm(f9_add(e[1], dn));
-                const F9 bj = sbj[k][j];
-#pragma unroll
-                for (int x = 0; x < 3; ++x) {
-                    // e (e - 1): e normal, e - 1 + 4r has limbs < 2^29 + 2^30; the product is normal
-                    const F9 q = f9_mul(e[x], f9_sub(e[x], one9));
-                    f9_cols_mac(cols[x], bj, q);
-                }
-                if (++pending == 4) {
-                    pending = 0;
-#pragma unroll
-                    for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
-                }
+                lo = f9_norm_reduce(f9_add(cur.t[0], f9_mul(f9_sub(cur.t[2], cur.t[0]), v)));
+                hi = f9_norm_reduce(f9_add(cur.t[1], f9_mul(f9_sub(cur.t[3], cur.t[1]), v)));
+                f9tab_st(col, b, lo);
+                f9tab_st(col, b + m, hi);
+            } else {
+                lo = cur.t[0];
+                hi = cur.t[1];
             }
+            const F9 bj = sbj[k][j];
+            const F9 dn = f9_norm(f9_sub(hi, lo));
+            // e (e - 1) at x = 0, 2, 3: e normal, e - 1 + 4r has limbs < 2^29 + 2^30; the product is normal
+            F9 e = lo;
+            f9_cols_mac(cols[0], bj, f9_mul(e, f9_sub(e, one9)));
+            e = f9_norm(f9_add(hi, dn));
+            f9_cols_mac(cols[1], bj, f9_mul(e, f9_sub(e, one9)));
+            e = f9_norm(f9_add(e, dn));
+            f9_cols_mac(cols[2], bj, f9_mul(e, f9_sub(e, one9)));
+            if (++pending == 4) {
+                pending = 0;
+#pragma unroll
+                for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
+            }
+            cur = nxt;
         }
         F9 bi[3];
         beta_line_fold(a, b, m, vprev9, bi);
@@ -793,11 +813,21 @@ __device__ __forceinline__ void binl_body(const BinArgs& a, const unsigned bx, c
         for (int x = 0; x < 3; ++x) {
             // at most 128 products below 2 r^2 each: the reduced sum is below 4.8 r, normal
             f9_cols_norm<17>(cols[x]);
-            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_redc(cols[x]))));
+            F9 t;
+#pragma unroll
+            for (int l = 0; l < 9; ++l) t.v[l] = tot_s[x][l][tid];
+            t = f9_norm_reduce(f9_add(t, f9_mul(bi[x], f9_redc(cols[x]))));
+#pragma unroll
+            for (int l = 0; l < 9; ++l) tot_s[x][l][tid] = t.v[l];
         }
     }
     const uint64_t blk = (uint64_t)by * gx + bx;
     {
+        F9 tot[3];
+#pragma unroll
+        for (int x = 0; x < 3; ++x)
+#pragma unroll
+            for (int l = 0; l < 9; ++l) tot[x].v[l] = tot_s[x][l][tid];
         const Fr s = block_sum_lazy<3>(tot, red);
         Fr* p = a.part + blk * 4;
         if (tid < 3) p[tid ? tid + 1 : 0] = s;
@@ -1281,12 +1311,16 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         ba.m = m;
         ba.part = ctx->partials + (uint64_t)nb_lin * 4;
         // few rows: split the columns over more blocks (rounds on the 64-bit words take them whole)
+        // Every (pair index, chunk) thread pays the beta_I fold and three reductions on top of its
+        // columns, about as much as one column costs: split only until the machine is full
+        // (two waves per SIMD: 2^17 threads).
+        constexpr uint64_t ZK_FILL_THREADS = 131072;
         int jc = nbits;
         if (t >= 2)
-            while ((uint64_t)((nbits + jc - 1) / jc) * m < 262144 && jc > 1) jc = (jc + 1) / 2;
+            while ((uint64_t)((nbits + jc - 1) / jc) * m < ZK_FILL_THREADS && jc > 1) jc = (jc + 1) / 2;
         unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
-        // one column per thread already: give the two slices their own threads as well
-        ba.ksplit = (t >= 2 && has_ga && jc == 1) ? 1 : 0;
+        // one column per thread and still not full: give the two slices their own threads as well
+        ba.ksplit = (t >= 2 && has_ga && jc == 1 && (uint64_t)chunks * m < ZK_FILL_THREADS) ? 1 : 0;
         if (ba.ksplit) chunks *= 2;
         const unsigned bx = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / chunks);
         const unsigned nb_bin = bx * chunks;
