@@ -245,17 +245,78 @@ __device__ inline void block_challenges(TsShared& S, DevState* st, int base, int
     }
 }
 
-// Closes a round: g_t(0..npts-1) (LDS, Montgomery, npts = 2..4) go to the proof and into
-// the transcript, the round's challenge v_t is drawn, the next claim g_t(v_t) is set.
-// Returns v_t to every thread.  Needs blockDim.x >= 128: while wave 0 hashes, wave 1
-// prepares the Lagrange coefficients c_k = g(k) / prod_{j != k} (k - j), and later the
-// canonical form of the challenge, so that after the hash only two dependent
-// multiplications remain:
+// g(v) from the prepared Lagrange coefficients c[k] = g(k) / prod_{j != k} (k - j), npts = 2..4,
+// by one wave (all 64 lanes call, no barrier inside); lane 0 returns the value.
 //   npts = 4: g(v) = (v-2)(v-3) [c0 (v-1) + c1 v] + v (v-1) [c2 (v-3) + c3 (v-2)]
 //   npts = 3: g(v) = (v-2) [c0 (v-1) + c1 v] + c2 v (v-1)
 //   npts = 2: g(v) = c0 (v-1) + c1 v
-__device__ inline Fr block_finalise_round(TsShared& S, DevState* st, const Fr* g, int npts,
-                                          uint32_t proof_off, int chal_idx) {
+// The operands of each level are selected per lane and multiplied by one call: lanes that
+// branch to separate calls would run them one after the other.
+__device__ inline Fr wave_lagrange(const Fr* c, int npts, const Fr& v) {
+    const int lane = threadIdx.x & 63;
+    const Fr one = fr_one();
+    const Fr v1 = fr_sub(v, one), v2 = fr_sub(v1, one), v3 = fr_sub(v2, one);
+    // level 1, lanes 0..5: c0 (v-1), c1 v, c2 (v-3) | c2 v, c3 (v-2), (v-2)(v-3), v (v-1)
+    Fr A = lane == 4 ? v2 : v;
+    if (lane < npts) A = c[lane];
+    Fr B = lane == 1 ? v : v1;
+    if (npts == 4) {
+        if (lane == 2 || lane == 4) B = v3;
+        else if (lane == 3) B = v2;
+    } else if (lane == 2) {
+        B = v;
+    }
+    const Fr p = fr_mul_ni(A, B);
+    // level 2, lanes 0, 1
+    Fr qa, qb, qc;   // products of lanes 2 lane, 2 lane + 1, 4 + lane
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+        qa.v[l] = __shfl(p.v[l], (2 * lane) & 63, 64);
+        qb.v[l] = __shfl(p.v[l], (2 * lane + 1) & 63, 64);
+        qc.v[l] = __shfl(p.v[l], (4 + lane) & 63, 64);
+    }
+    Fr r;
+    if (npts == 2) {
+        r = fr_add(qa, qb);   // lane 0: q0 + q1
+    } else {
+        Fr A2, B2;
+        if (npts == 4) {
+            A2 = qc;                   // lane 0: (v-2)(v-3), lane 1: v (v-1)
+            B2 = fr_add(qa, qb);       // lane 0: q0 + q1, lane 1: q2 + q3
+        } else {
+            A2 = lane == 0 ? v2 : qa;  // lane 1: q2 = c2 v
+            B2 = lane == 0 ? fr_add(qa, qb) : v1;
+        }
+        r = fr_mul_ni(A2, B2);
+        Fr r1;
+#pragma unroll
+        for (int l = 0; l < 8; ++l) r1.v[l] = __shfl(r.v[l], 1, 64);
+        r = fr_add(r, r1);
+    }
+    return r;
+}
+
+// The claim of the last finished round may still be owed: a round kernel needs only the
+// challenge, so the evaluation g_t(v_t) is left to whoever needs the claim next, who does it
+// in a spare wave next to other work.  One wave calls this; afterwards st->claim is current.
+__device__ inline void wave_resolve_claim(DevState* st) {
+    const uint32_t npts = st->lag_npts;   // wave-uniform
+    if (npts) {
+        const Fr c = wave_lagrange(st->lag, (int)npts, st->chal[st->lag_chal]);
+        if ((threadIdx.x & 63) == 0) {
+            st->claim = c;
+            st->lag_npts = 0;
+        }
+    }
+}
+
+// First part of closing a round: g_t(0..npts-1) (LDS, Montgomery, npts = 2..4) go to the proof
+// and into the transcript, the round's challenge v_t is drawn and returned to every thread.
+// The Lagrange coefficients of g_t are left in S.tmp[0..npts) for the claim g_t(v_t).
+// Needs blockDim.x >= 192: while wave 0 hashes, wave 1 prepares the coefficients and wave 2
+// later writes the canonical form of the challenge.
+__device__ inline Fr block_round_challenge(TsShared& S, DevState* st, const Fr* g, int npts,
+                                           uint32_t proof_off, int chal_idx) {
     const int tid = threadIdx.x;
     uint32_t* proof_dst = (uint32_t*)(st->proof + proof_off);
     __syncthreads();
@@ -313,75 +374,33 @@ __device__ inline Fr block_finalise_round(TsShared& S, DevState* st, const Fr* g
     if (tid < 8) S.state[tid] = S.dig[2][tid];
     if (tid == 8) S.nblk += 1;
     if (tid == 0) st->chal[chal_idx] = v;
-    // first level of the Lagrange sum (wave 0, one product per lane) | canonical v (wave 1).
-    // The operands are selected per lane and multiplied by one call: lanes that branch to
-    // separate calls would run them one after the other.
-    const Fr one = fr_one();
-    const Fr v1 = fr_sub(v, one), v2 = fr_sub(v1, one), v3 = fr_sub(v2, one);
-    if (tid < 6) {
-        // npts = 4: c0 (v-1), c1 v, c2 (v-3), c3 (v-2), (v-2)(v-3), v (v-1)
-        // npts = 3: c0 (v-1), c1 v, c2 v;   npts = 2: c0 (v-1), c1 v
-        Fr A = tid == 4 ? v2 : v;
-        if (tid < 4) A = S.tmp[tid];
-        Fr B = tid == 1 ? v : v1;                // lanes 0, 1, and lane 5: v - 1
-        if (npts == 4) {
-            if (tid == 2 || tid == 4) B = v3;
-            else if (tid == 3) B = v2;
-        } else if (tid == 2) {
-            B = v;
-        }
-        const Fr p = fr_mul_ni(A, B);
-#pragma unroll
-        for (int l = 0; l < 8; ++l) S.dig[4 + tid][l] = p.v[l];
-    } else if (tid == 64) {
+    if (tid == 128) {
         Fr plain = fr_from_mont_ni(v);
         uint32_t* le = (uint32_t*)(st->chal_le + 32 * (size_t)chal_idx);
 #pragma unroll
         for (int l = 0; l < 8; ++l) le[l] = plain.v[l];
     }
-    __syncthreads();
-    if (tid < 2) {
-        Fr q[6];
-#pragma unroll
-        for (int j = 0; j < 6; ++j)
-#pragma unroll
-            for (int l = 0; l < 8; ++l) q[j].v[l] = S.dig[4 + j][l];
-        Fr r;
-        if (npts == 2) {
-            r = tid == 0 ? fr_add(q[0], q[1]) : fr_zero();
-        } else {
-            // npts = 4: (v-2)(v-3) [q0 + q1], v (v-1) [q2 + q3];  npts = 3: (v-2) [q0 + q1], q2 (v-1)
-            Fr A, B;
-            if (npts == 4) {
-                A = tid == 0 ? q[4] : q[5];
-                B = tid == 0 ? fr_add(q[0], q[1]) : fr_add(q[2], q[3]);
-            } else {
-                A = tid == 0 ? v2 : q[2];
-                B = tid == 0 ? fr_add(q[0], q[1]) : v1;
-            }
-            r = fr_mul_ni(A, B);
-        }
-#pragma unroll
-        for (int l = 0; l < 8; ++l) S.dig[10 + tid][l] = r.v[l];
+    return v;
+}
+
+// Closes a round completely: challenge, then the next claim g_t(v_t) in st->claim.
+__device__ inline Fr block_finalise_round(TsShared& S, DevState* st, const Fr* g, int npts,
+                                          uint32_t proof_off, int chal_idx) {
+    const Fr v = block_round_challenge(S, st, g, npts, proof_off, chal_idx);
+    if ((threadIdx.x >> 6) == 1) {
+        const Fr c = wave_lagrange(S.tmp, npts, v);
+        if ((threadIdx.x & 63) == 0) st->claim = c;
     }
     __syncthreads();
-    if (tid == 0) {
-        Fr r0, r1;
-#pragma unroll
-        for (int l = 0; l < 8; ++l) {
-            r0.v[l] = S.dig[10][l];
-            r1.v[l] = S.dig[11][l];
-        }
-        st->claim = fr_add(r0, r1);
-    }
     return v;
 }
 
 // Sums per-block partial sums part[b * npts + x], b < nblk, into g[x] (LDS): wave x
-// handles evaluation x on its own.  Needs blockDim.x >= 64 * npts.
-__device__ inline void block_reduce_partials(const Fr* part, int nblk, int npts, Fr* g) {
+// handles evaluation x on its own (skip1: evaluation 1 is not summed, wave 1 is free for
+// other work before the closing barrier).  Needs blockDim.x >= 64 * npts.
+__device__ inline void block_reduce_partials(const Fr* part, int nblk, int npts, Fr* g, bool skip1 = false) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (wave < npts) {
+    if (wave < npts && !(skip1 && wave == 1)) {
         Fr s = fr_zero();
         // up to eight rows of 64 partials at a time, their loads issued together: the loop is
         // bound by memory latency

@@ -131,17 +131,33 @@ struct FinArgs {
 __global__ __launch_bounds__(ZK_BLOCK) void k_sc_finalise(FinArgs a) {
     __shared__ TsShared S;
     __shared__ Fr g[ZK_MAX_EVALS + 1];
+    __shared__ Fr claim_s;
     DevState* st = a.st;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     block_ts_load(S, st);
-    block_reduce_partials(a.part, a.nblk, a.npts, g);
-    if (a.derive1 && threadIdx.x == 0) g[1] = fr_sub(st->claim, g[0]);
+    // g(1) comes from the running claim, which the previous round may still owe: wave 1 has no
+    // partial sums to add in that case and evaluates it meanwhile
+    if (a.derive1 && wave == 1) {
+        wave_resolve_claim(st);
+        if (lane == 0) claim_s = st->claim;
+    }
+    block_reduce_partials(a.part, a.nblk, a.npts, g, a.derive1 != 0);
+    if (a.derive1 && threadIdx.x == 0) g[1] = fr_sub(claim_s, g[0]);
     __syncthreads();
     if (a.first) {
         if (threadIdx.x == 0) g[ZK_MAX_EVALS] = fr_add(g[0], g[1]);
         __syncthreads();
         block_absorb_frs(S, 'c', &g[ZK_MAX_EVALS], 1, (uint32_t*)(st->proof + a.claim_off));
     }
-    block_finalise_round(S, st, g, a.npts, a.proof_off, a.chal_idx);
+    block_round_challenge(S, st, g, a.npts, a.proof_off, a.chal_idx);
+    // the next claim g_t(v_t) is owed: whoever needs it evaluates it from these coefficients
+    if (wave == 1) {
+        if (lane < a.npts) st->lag[lane] = S.tmp[lane];
+        if (lane == 0) {
+            st->lag_npts = (uint32_t)a.npts;
+            st->lag_chal = (uint32_t)a.chal_idx;
+        }
+    }
     block_ts_store(S, st);
 }
 
@@ -201,6 +217,7 @@ __global__ __launch_bounds__(64) void k_sc_finish(FinishArgs a) {
             Fr c0 = f[0];
             for (int k = 1; k < a.K; ++k) c0 = fr_mul_ni(c0, f[k]);
             st->claim = c0;
+            st->lag_npts = 0;
             f[3] = c0;
         }
         __syncthreads();
@@ -234,6 +251,8 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_tail(ScTailArgs a) {
     uint64_t m = a.ra.m;
     F9 v = fr_unpack(st->chal[a.first_chal]);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // the claim of the round before may still be owed; it is first read after a barrier
+    if (wave == 3) wave_resolve_claim(st);
     int el_cur = -1;   // buffer of `el` that holds the current tables; -1: they are in memory
     for (int t = 0; t < a.rounds; ++t) {
         if (m > 64) {
@@ -312,9 +331,14 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_tail(ScTailArgs a) {
             el_cur = nxt;
         }
         __syncthreads();
-        Fr vr = block_finalise_round(S, st, g, K + 1, a.rounds_off + (uint32_t)t * (K + 1) * 32,
-                                     a.first_chal + 1 + t);
-        __syncthreads();   // the claim and the folded tables are read by other threads next round
+        Fr vr = block_round_challenge(S, st, g, K + 1, a.rounds_off + (uint32_t)t * (K + 1) * 32,
+                                      a.first_chal + 1 + t);
+        // the next claim is evaluated by wave 3 while the others fold with the new challenge;
+        // it is read after the barriers of the next round's sums
+        if (wave == 3) {
+            const Fr c = wave_lagrange(S.tmp, K + 1, vr);
+            if (lane == 0) st->claim = c;
+        }
         v = fr_unpack(vr);
         m >>= 1;
     }

@@ -139,6 +139,7 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_claims(ClaimsArgs a) {
     Fr claim = fr_zero();
     for (int q = 0; q < 4; ++q) claim = fr_add(claim, fr_mul_ni(st->weights[q], c[q]));
     st->claim = claim;
+    st->lag_npts = 0;
     Fr plain = fr_from_mont_ni(claim);
     uint32_t* dst = (uint32_t*)(st->proof + a.claim0_off);
     for (int l = 0; l < 8; ++l) dst[l] = plain.v[l];
@@ -918,6 +919,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void k_zk_tail(TailArgs a) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     DevState* st = a.st;
     block_ts_load(TS, st);
+    if (wave == 3) wave_resolve_claim(st);   // the last i-round may still owe its claim; read after barriers
     const int J = 1 << a.lj, nbits = a.q_bits + a.r_bits;
     const Fr one = fr_one();
     Fr vlast = fr_zero();

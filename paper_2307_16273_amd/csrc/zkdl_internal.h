@@ -22,8 +22,11 @@ struct DevState {
     uint32_t ts_state[8];   // transcript: SHA-256 chaining value after the last block of the stream
     uint32_t err;           // bit 0: zkReLU input out of range
     uint32_t ts_nblk[2];    // transcript: number of 64-byte blocks in the stream (low, high word)
-    uint32_t pad0[5];
-    Fr claim;               // claim of the running sumcheck (Montgomery)
+    uint32_t lag_npts;      // != 0: claim is owed, claim = g(chal[lag_chal]) with the coefficients lag[]
+    uint32_t lag_chal;
+    uint32_t pad0[3];
+    Fr claim;               // claim of the running sumcheck (Montgomery); current if lag_npts == 0
+    Fr lag[4];              // Lagrange coefficients of the last round polynomial
     Fr inv2, inv6;          // constants of the Lagrange formulas
     Fr weights[8];          // zkReLU: r^2, r, r'r^2, r'r, r'
     Fr scal[64];            // scalars handed between kernels (claims, finals)
