@@ -29,16 +29,15 @@
  *  - proof / proof_len: *proof_len holds the capacity in bytes on entry and the
  *    bytes written on return.  ZKDL_ESMALL sets *proof_len to the size needed.
  *
- * Transcript (this library's own format).  The transcript is one byte stream,
- * always a whole number of 64-byte blocks; every value derived from it is a
- * plain SHA-256 of an extension of it:
- *   stream_0         = "zkdl-mi355x/v2" zero-padded to 56 bytes || u64le(seed)
- *   absorb(label, m) : stream <- stream || pad64(u8(|label|) || label ||
- *                      u64le(|m|) || m), pad64 = zero bytes up to the next
- *                      multiple of 64, |label| <= 32
+ * Transcript (this library's own format).  The transcript is one byte stream;
+ * every value derived from it is a plain SHA-256 of an extension of it:
+ *   stream_0         = "zkdl-mi355x/v3" zero-padded to 56 bytes || u64le(seed)
+ *   absorb(label, m) : stream <- stream || u8(|label|) || label || u64le(|m|)
+ *                      || m, |label| <= 32
  *   challenges(n)    : c_i = int_le(SHA256(stream || 0xF0 || u32le(i)) ||
  *                      SHA256(stream || 0xF1 || u32le(i))) mod r for i < n,
- *                      then stream <- stream || 0xF2 || 63 zero bytes
+ *                      then stream <- stream || 0xF2 || zero bytes up to the
+ *                      next multiple of 64
  *   digest           = SHA256(stream)
  * Field elements are absorbed as zkdl_fr bytes.  A sumcheck absorbs its header
  * words under the protocol's name, claim_0 under "c" (where the verifier cannot

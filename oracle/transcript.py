@@ -5,25 +5,27 @@ element after every round polynomial (App. B, both protocols).  Here each such
 message is replaced by a hash of everything sent so far.  The byte format is
 this build's own; the HIP library implements the same format independently.
 
-The transcript is ONE byte stream, always a whole number of 64-byte blocks, and
-everything derived from it is a plain SHA-256 of a prefix-extension of it:
+The transcript is ONE byte stream, and everything derived from it is a plain SHA-256
+of an extension of it:
 
-  stream_0          = "zkdl-mi355x/v2" zero-padded to 56 bytes || u64le(seed)      (one block)
-  absorb(label, m)  : stream <- stream || pad64(u8(len label) || label || u64le(len m) || m)
-                      (pad64: zero bytes up to the next multiple of 64; len label <= 32)
+  stream_0          = "zkdl-mi355x/v3" zero-padded to 56 bytes || u64le(seed)      (64 bytes)
+  absorb(label, m)  : stream <- stream || u8(len label) || label || u64le(len m) || m
+                      (len label <= 32)
   challenges(n)     : for i < n: d0 = SHA256(stream || 0xF0 || u32le(i)),
                                  d1 = SHA256(stream || 0xF1 || u32le(i)),
                                  c_i = int_le(d0 || d1) mod r
-                      then stream <- stream || 0xF2 || 63 zero bytes   (n = 0: nothing happens)
+                      then stream <- stream || 0xF2 || zero bytes up to the next multiple of 64
+                      (n = 0: nothing happens)
   challenge()       = challenges(1)[0]
   digest()          = SHA256(stream)
 
-Because the stream is block-aligned, a prover needs the SHA-256 chaining value
-after the last block only: an absorb costs one compression per 64 bytes of
-message, and each hash of a draw is one more compression from that chaining
-value (its block holds the five bytes and the padding), all of them independent.
-The n challenges of one draw are therefore one hash latency on a parallel
-machine, not n.
+A prover keeps the SHA-256 chaining value after the last whole block and the bytes of the
+unfinished block.  After a draw the stream is block-aligned, so the usual step of a sumcheck
+round - absorb a 106-byte frame, draw one challenge - is one compression for the frame's first
+64 bytes, followed by three independent compressions from that chaining value: the two hashes
+of the draw (their last block holds the frame's remaining 42 bytes, the five bytes of the draw
+and the padding) and the block that extends the stream.  The n challenges of one draw are one
+hash latency on a parallel machine, not n.
 
 Field elements are absorbed as 32-byte canonical little-endian strings.
 Test infrastructure; not used by the product.
@@ -33,22 +35,26 @@ import struct
 
 from .field import R_MOD, to_le
 
-DOMAIN = b"zkdl-mi355x/v2"
+DOMAIN = b"zkdl-mi355x/v3"
 MAX_LABEL = 32
 
 
 class Transcript:
     def __init__(self, seed=0):
         self._h = hashlib.sha256()
-        self._h.update(DOMAIN + b"\x00" * (56 - len(DOMAIN)) + struct.pack("<Q", seed))
+        self._len = 0
+        self._append(DOMAIN + b"\x00" * (56 - len(DOMAIN)) + struct.pack("<Q", seed))
         self.challenges = []          # every challenge drawn, in order
+
+    def _append(self, data):
+        self._h.update(data)
+        self._len += len(data)
 
     def absorb(self, label, data):
         label = bytes(label)
         data = bytes(data)
         assert len(label) <= MAX_LABEL
-        frame = bytes([len(label)]) + label + struct.pack("<Q", len(data)) + data
-        self._h.update(frame + b"\x00" * (-len(frame) % 64))
+        self._append(bytes([len(label)]) + label + struct.pack("<Q", len(data)) + data)
 
     def absorb_fr(self, label, elements):
         self.absorb(label, b"".join(to_le(e) for e in elements))
@@ -67,7 +73,8 @@ class Transcript:
             idx = struct.pack("<I", i)
             out.append(int.from_bytes(self._fork(b"\xf0" + idx) + self._fork(b"\xf1" + idx), "little") % R_MOD)
         if n > 0:
-            self._h.update(b"\xf2" + b"\x00" * 63)
+            self._append(b"\xf2")
+            self._append(b"\x00" * (-self._len % 64))
         self.challenges.extend(out)
         return out
 

@@ -466,15 +466,17 @@ static int call_begin(zkdl_ctx* ctx, zkdl_transcript* tr) {
     ctx->proof_len = 0;
     ctx->pend_len = 0;
     g_patches.clear();
-    // state + cleared error word
-    memset(ctx->host_stage, 0, 64);
+    // transcript state; error word and owed claim cleared
+    memset(ctx->host_stage, 0, ZK_STATE_HEAD);
     {
         DevState* h = (DevState*)ctx->host_stage;
         for (int i = 0; i < 8; ++i) h->ts_state[i] = tr->s.h[i];
         h->ts_nblk[0] = (uint32_t)tr->s.nblk;
         h->ts_nblk[1] = (uint32_t)(tr->s.nblk >> 32);
+        h->ts_fill = tr->s.fill;
+        for (uint32_t i = 0; i < tr->s.fill; ++i) h->ts_buf[i >> 2] |= (uint32_t)tr->s.buf[i] << (24 - 8 * (i & 3));
     }
-    ZK_HIP(ctx, hipMemcpyAsync(ctx->dev, ctx->host_stage, 64, hipMemcpyHostToDevice, ctx->stream));
+    ZK_HIP(ctx, hipMemcpyAsync(ctx->dev, ctx->host_stage, ZK_STATE_HEAD, hipMemcpyHostToDevice, ctx->stream));
     return ZKDL_OK;
 }
 
@@ -505,6 +507,9 @@ static int call_end(zkdl_ctx* ctx, zkdl_transcript* tr, int rc_in, uint8_t* proo
     if (h->err & 1u) return ZKDL_ERANGE;
     for (int i = 0; i < 8; ++i) tr->s.h[i] = h->ts_state[i];
     tr->s.nblk = ((uint64_t)h->ts_nblk[1] << 32) | h->ts_nblk[0];
+    tr->s.fill = h->ts_fill;
+    for (uint32_t i = 0; i < 64; ++i)
+        tr->s.buf[i] = i < h->ts_fill ? (uint8_t)(h->ts_buf[i >> 2] >> (24 - 8 * (i & 3))) : 0;
     int rc = ZKDL_OK;
     if (proof_len) {
         if (!proof || *proof_len < ctx->proof_len) {

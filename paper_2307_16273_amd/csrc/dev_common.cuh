@@ -89,14 +89,17 @@ __device__ __forceinline__ Fr block_sum_lazy(const F9 (&x)[N], uint32_t* red) {
 
 constexpr int TS_MAX_ABSORB = 8;     // field elements per device-side absorb
 constexpr int TS_MAX_DRAW = 64;      // challenges per block_challenges chunk
-constexpr int TS_MAX_FRAME_BLOCKS = (10 + 32 * TS_MAX_ABSORB + 63) / 64;
+constexpr int TS_MAX_BLOCKS = 8;     // whole blocks one append may complete (ZK_PEND_CAP + 63 bytes)
 
 // LDS working set of the transcript steps
 struct TsShared {
-    uint32_t state[8];                       // chaining value after the last block of the stream
-    uint64_t nblk;                           // blocks in the stream
-    uint32_t msg[16 * TS_MAX_FRAME_BLOCKS];  // frame being absorbed, big-endian words
-    uint32_t wk[TS_MAX_FRAME_BLOCKS + 3][64];// schedules: frame blocks, then a draw's three blocks
+    uint32_t state[8];                       // chaining value after the last whole block of the stream
+    uint64_t nblk;                           // whole blocks in the stream
+    uint32_t fill;                           // bytes of the unfinished block
+    uint32_t bufsel;                         // which of buf[] holds them
+    uint32_t buf[2][16];                     // unfinished block, big-endian words, zero beyond fill
+    uint32_t msg[16 * (TS_MAX_BLOCKS + 3)];  // blocks being absorbed, then a draw's three blocks
+    uint32_t wk[TS_MAX_BLOCKS + 3][64];      // their schedules
     uint32_t canon[TS_MAX_ABSORB][8];        // canonical little-endian limbs being absorbed
     uint32_t dig[2 * TS_MAX_DRAW + 1][8];    // digests of a challenge draw
     Fr tmp[TS_MAX_ABSORB];
@@ -105,74 +108,185 @@ struct TsShared {
 
 __device__ __forceinline__ void block_ts_load(TsShared& S, const DevState* st) {
     if (threadIdx.x < 8) S.state[threadIdx.x] = st->ts_state[threadIdx.x];
-    if (threadIdx.x == 8) S.nblk = ((uint64_t)st->ts_nblk[1] << 32) | st->ts_nblk[0];
+    if (threadIdx.x >= 16 && threadIdx.x < 32) S.buf[0][threadIdx.x - 16] = st->ts_buf[threadIdx.x - 16];
+    if (threadIdx.x == 8) {
+        S.nblk = ((uint64_t)st->ts_nblk[1] << 32) | st->ts_nblk[0];
+        S.fill = st->ts_fill;
+        S.bufsel = 0;
+    }
     __syncthreads();
 }
 
 __device__ __forceinline__ void block_ts_store(const TsShared& S, DevState* st) {
     __syncthreads();
     if (threadIdx.x < 8) st->ts_state[threadIdx.x] = S.state[threadIdx.x];
+    if (threadIdx.x >= 16 && threadIdx.x < 32) st->ts_buf[threadIdx.x - 16] = S.buf[S.bufsel][threadIdx.x - 16];
     if (threadIdx.x == 8) {
         st->ts_nblk[0] = (uint32_t)S.nblk;
         st->ts_nblk[1] = (uint32_t)(S.nblk >> 32);
+        st->ts_fill = S.fill;
     }
 }
 
-// blocks of the frame of `count` field elements under a one-character label
-__device__ __forceinline__ uint32_t ts_frame_blocks(int count) { return (10u + 32u * (uint32_t)count + 63u) / 64u; }
+// byte q of the block that closes a draw hash (tag 0xF0 / 0xF1: tag, u32le(idx), 0x80, zeros,
+// 64-bit big-endian bit length at the end of block `last`) or that extends the stream after a
+// draw (tag 0xF2: tag, zeros), for an unfinished block of `rem` bytes given by `rest`;
+// blk = 0 or 1 is the block the byte belongs to
+template <class RestByte>
+__device__ __forceinline__ uint32_t ts_draw_byte(uint32_t blk, uint32_t q, uint32_t rem, RestByte rest, uint32_t tag,
+                                                 uint32_t idx, uint32_t last, uint64_t bits) {
+    const uint32_t p = 64 * blk + q;
+    if (p < rem) return rest(p);
+    if (p == rem) return tag;
+    if (tag == 0xF2u) return 0;
+    if (p <= rem + 4) return (idx >> (8 * (p - rem - 1))) & 0xffu;
+    if (p == rem + 5) return 0x80u;
+    if (blk == last && q >= 56) return (uint32_t)(bits >> (8 * (63 - q))) & 0xffu;
+    return 0;
+}
 
-// stream <- stream || pad64(0x01 || label || u64le(32 count) || canon[0..count)) for a
-// one-character label; canon must be complete (a barrier is taken first).  Lane j of
-// wave 0 prepares the schedule of frame block j, then lane 0 runs the rounds block after
-// block.  With draw1 the three blocks of a single-challenge draw that follows this absorb
-// (halves 0xF0, 0xF1 at index 0, and the 0xF2 block) get their schedules in the same step,
-// in wk[nb .. nb + 3), nb = ts_frame_blocks(count): they depend on the block count only.
-__device__ inline void block_absorb1(TsShared& S, char label, int count, bool draw1) {
+// Appends `len` bytes, given by frame(q), to the stream.  Lane j of wave 0 prepares the
+// schedule of whole block j, then lane 0 runs the rounds block after block.  With draw1, and
+// if the unfinished block that remains leaves room (at most 50 bytes), the three blocks of a
+// single-challenge draw that follows (the closing blocks of the two hashes at index 0, and the
+// block that extends the stream) get their schedules in the same step, in wk[nb .. nb + 3),
+// where nb, the number of whole blocks completed, is returned; -1 - nb if they were not
+// prepared.  frame(q) may read S.canon; a barrier is taken first.
+template <class FrameByte>
+__device__ __forceinline__ int block_append(TsShared& S, uint32_t len, FrameByte frame, bool draw1) {
     __syncthreads();
-    const uint32_t total = 10u + 32u * (uint32_t)count;
-    const uint32_t nb = ts_frame_blocks(count);
-    const uint32_t data_len = 32u * (uint32_t)count;
-    // every thread builds whole message words, byte by byte
-    for (uint32_t j = threadIdx.x; j < 16 * nb; j += blockDim.x) {
+    const uint32_t fill = S.fill, sel = S.bufsel;
+    const uint32_t total = fill + len;
+    const uint32_t nb = total / 64, rem = total % 64;
+    const bool fused = draw1 && rem <= 50;
+    const uint64_t nblk_after = S.nblk + nb;
+    const uint64_t bits = (nblk_after * 64u + rem + 5u) * 8u;
+    auto stream_byte = [&](uint32_t p) -> uint32_t {   // byte p counted from the start of the unfinished block
+        if (p < fill) return (S.buf[sel][p >> 2] >> (24 - 8 * (p & 3))) & 0xffu;
+        return frame(p - fill) & 0xffu;
+    };
+    auto rest_byte = [&](uint32_t p) -> uint32_t { return stream_byte(64 * nb + p); };
+    // every thread builds whole words, byte by byte: the whole blocks, the new unfinished block,
+    // the draw's blocks
+    const uint32_t nwords = 16 * nb + 16 + (fused ? 48u : 0u);
+    for (uint32_t j = threadIdx.x; j < nwords; j += blockDim.x) {
         uint32_t word = 0;
+        if (j < 16 * nb) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const uint32_t p = 4 * j + b;
-            uint32_t byte;
-            if (p == 0) byte = 1;
-            else if (p == 1) byte = (uint8_t)label;
-            else if (p < 10) byte = (p - 2 < 4) ? ((data_len >> (8 * (p - 2))) & 0xffu) : 0u;
-            else if (p < total) {
-                const uint32_t q = p - 10;
-                byte = (S.canon[q >> 5][(q & 31) >> 2] >> (8 * (q & 3))) & 0xffu;
-            } else byte = 0;
-            word = (word << 8) | byte;
+            for (int b = 0; b < 4; ++b) word = (word << 8) | stream_byte(4 * j + b);
+            S.msg[j] = word;
+        } else if (j < 16 * nb + 16) {
+            const uint32_t q0 = 4 * (j - 16 * nb);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) word = (word << 8) | (q0 + b < rem ? rest_byte(q0 + b) : 0u);
+            S.buf[sel ^ 1][j - 16 * nb] = word;
+        } else {
+            const uint32_t k = j - 16 * nb - 16, t = k >> 4, q0 = 4 * (k & 15);
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                word = (word << 8) | ts_draw_byte(0, q0 + b, rem, rest_byte, 0xF0u + t, 0u, 0u, bits);
+            S.msg[16 * nb + k] = word;
         }
-        S.msg[j] = word;
     }
     __syncthreads();
-    const uint64_t nblk_after = S.nblk + nb;
-    if (threadIdx.x < nb + (draw1 ? 3u : 0u)) {
+    if (threadIdx.x < nb + (fused ? 3u : 0u)) {
         sha::Words16 w;
-        if (threadIdx.x < nb) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) w.v[i] = S.msg[16 * threadIdx.x + i];
-        } else {
-            w = sha::draw_block_words(0xF0u + (threadIdx.x - nb), 0u, nblk_after);
-        }
+        for (int i = 0; i < 16; ++i) w.v[i] = S.msg[16 * threadIdx.x + i];
         sha::schedule_wk_lds(w, (sha::lds_u32_ptr)S.wk[threadIdx.x]);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        sha::Words8 h;
+        if (nb > 0) {
+            sha::Words8 h;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
-        for (uint32_t blk = 0; blk < nb; ++blk) h = sha::rounds_lds(h, (sha::lds_u32_cptr)S.wk[blk]);
+            for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
+            for (uint32_t blk = 0; blk < nb; ++blk) h = sha::rounds_lds(h, (sha::lds_u32_cptr)S.wk[blk]);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) S.state[i] = h.v[i];
+            for (int i = 0; i < 8; ++i) S.state[i] = h.v[i];
+        }
         S.nblk = nblk_after;
+        S.fill = rem;
+        S.bufsel = sel ^ 1;
     }
     __syncthreads();
+    return fused ? (int)nb : -1 - (int)nb;
+}
+
+// stream <- stream || 0x01 || label || u64le(32 count) || canon[0..count) for a one-character
+// label; canon must be complete (a barrier is taken first).  Return value as block_append.
+// On a block-aligned stream - every round after a draw - the words are put together from
+// whole limbs: the data start at byte 10, so a message word is the upper half of one limb and
+// the lower half of the next, bytes swapped.
+__device__ inline int block_absorb1(TsShared& S, char label, int count, bool draw1) {
+    const uint32_t data_len = 32u * (uint32_t)count;
+    __syncthreads();
+    if (S.fill != 0) {
+        auto frame = [&](uint32_t q) -> uint32_t {
+            if (q == 0) return 1u;
+            if (q == 1) return (uint32_t)(uint8_t)label;
+            if (q < 10) return q - 2 < 4 ? (data_len >> (8 * (q - 2))) & 0xffu : 0u;
+            const uint32_t d = q - 10;
+            return (S.canon[d >> 5][(d & 31) >> 2] >> (8 * (d & 3))) & 0xffu;
+        };
+        return block_append(S, 10u + data_len, frame, draw1);
+    }
+    const uint32_t sel = S.bufsel;
+    const uint32_t total = 10u + data_len, nb = total / 64, rem = total % 64;   // rem % 4 == 2
+    const bool fused = draw1 && rem <= 50;
+    const uint64_t nblk_after = S.nblk + nb;
+    const uint64_t bits = (nblk_after * 64u + rem + 5u) * 8u;
+    const uint32_t nlimb = 8u * (uint32_t)count;
+    auto frame_word = [&](uint32_t k) -> uint32_t {   // bytes 4k .. 4k+3 of the frame, first byte on top
+        if (k == 0) return (1u << 24) | ((uint32_t)(uint8_t)label << 16) | ((data_len & 0xffu) << 8) | ((data_len >> 8) & 0xffu);
+        if (k == 1) return 0u;                        // length bytes 2..5: data_len < 2^16
+        const uint32_t ip = k - 3, in = k - 2;        // limbs that end / begin in this word
+        const uint32_t lp = (k >= 3 && ip < nlimb) ? S.canon[ip >> 3][ip & 7] : 0u;
+        const uint32_t ln = in < nlimb ? S.canon[in >> 3][in & 7] : 0u;
+        return (((lp >> 16) & 0xffu) << 24) | ((lp >> 24) << 16) | ((ln & 0xffu) << 8) | ((ln >> 8) & 0xffu);
+    };
+    const uint32_t wr = rem >> 2;                     // word of the unfinished block that takes the tag
+    const uint32_t nwords = 16 * nb + 16 + (fused ? 48u : 0u);
+    for (uint32_t j = threadIdx.x; j < nwords; j += blockDim.x) {
+        if (j < 16 * nb) {
+            S.msg[j] = frame_word(j);
+        } else if (j < 16 * nb + 16) {
+            S.buf[sel ^ 1][j - 16 * nb] = frame_word(j);
+        } else {
+            const uint32_t k = j - 16 * nb - 16, t = k >> 4, i = k & 15;
+            uint32_t word = frame_word(16 * nb + i);
+            if (i == wr) word |= (0xF0u + t) << 8;                    // tag; the index bytes are zero
+            if (t < 2) {
+                if (i == wr + 1) word |= 0x80u;
+                if (i == 14) word = (uint32_t)(bits >> 32);
+                if (i == 15) word = (uint32_t)bits;
+            }
+            S.msg[16 * nb + k] = word;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < nb + (fused ? 3u : 0u)) {
+        sha::Words16 w;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) w.v[i] = S.msg[16 * threadIdx.x + i];
+        sha::schedule_wk_lds(w, (sha::lds_u32_ptr)S.wk[threadIdx.x]);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (nb > 0) {
+            sha::Words8 h;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
+            for (uint32_t blk = 0; blk < nb; ++blk) h = sha::rounds_lds(h, (sha::lds_u32_cptr)S.wk[blk]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) S.state[i] = h.v[i];
+        }
+        S.nblk = nblk_after;
+        S.fill = rem;
+        S.bufsel = sel ^ 1;
+    }
+    __syncthreads();
+    return fused ? (int)nb : -1 - (int)nb;
 }
 
 // canonical forms of vals[0..count) (Montgomery, LDS or global) -> proof words (if
@@ -191,24 +305,41 @@ __device__ inline void block_absorb_frs(TsShared& S, char label, const Fr* vals,
 }
 
 // draws `count` challenges into st->chal[base..), st->chal_le; one stream extension.
-// The first one is also left in S.v.
+// The first one is also left in S.v.  Works for any unfinished block (the closing blocks of
+// a hash are two when it holds more than 50 bytes).
 __device__ inline void block_challenges(TsShared& S, DevState* st, int base, int count) {
     if (count <= 0) return;
     __syncthreads();
+    const uint32_t rem = S.fill, sel = S.bufsel;
+    const uint32_t last = rem + 14 > 64 ? 1u : 0u;
+    const uint64_t bits = (S.nblk * 64u + rem + 5u) * 8u;
+    auto rest_byte = [&](uint32_t p) -> uint32_t { return (S.buf[sel][p >> 2] >> (24 - 8 * (p & 3))) & 0xffu; };
     for (int c0 = 0; c0 < count; c0 += TS_MAX_DRAW) {
         const int n = count - c0 < TS_MAX_DRAW ? count - c0 : TS_MAX_DRAW;
-        const bool last = c0 + n >= count;
-        const int jobs = 2 * n + (last ? 1 : 0);
+        const bool lastchunk = c0 + n >= count;
+        const int jobs = 2 * n + (lastchunk ? 1 : 0);
         for (int t = threadIdx.x; t < jobs; t += blockDim.x) {
             sha::Words8 h;
 #pragma unroll
             for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
             const bool elem = t < 2 * n;
-            const sha::Words16 w = sha::draw_block_words(elem ? 0xF0u + (uint32_t)(t & 1) : 0xF2u,
-                                                         elem ? (uint32_t)(c0 + (t >> 1)) : 0u, S.nblk);
-            const sha::Words8 out = sha::compress_ni(h, w);
+            const uint32_t tag = elem ? 0xF0u + (uint32_t)(t & 1) : 0xF2u;
+            const uint32_t idx = elem ? (uint32_t)(c0 + (t >> 1)) : 0u;
+            const uint32_t nbk = elem ? last + 1 : 1u;
+            for (uint32_t blk = 0; blk < nbk; ++blk) {
+                sha::Words16 w;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) S.dig[t][i] = out.v[i];
+                for (int i = 0; i < 16; ++i) {
+                    uint32_t word = 0;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        word = (word << 8) | ts_draw_byte(blk, 4 * i + b, rem, rest_byte, tag, idx, last, bits);
+                    w.v[i] = word;
+                }
+                h = sha::compress_ni(h, w);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) S.dig[t][i] = h.v[i];
         }
         __syncthreads();
         // wide reduction: one lane per half, then one lane per element
@@ -237,9 +368,12 @@ __device__ inline void block_challenges(TsShared& S, DevState* st, int base, int
             for (int l = 0; l < 8; ++l) le[l] = plain.v[l];
         }
         __syncthreads();
-        if (last) {
+        if (lastchunk) {
             if (threadIdx.x < 8) S.state[threadIdx.x] = S.dig[2 * n][threadIdx.x];
-            if (threadIdx.x == 8) S.nblk += 1;
+            if (threadIdx.x == 8) {
+                S.nblk += 1;
+                S.fill = 0;
+            }
         }
         __syncthreads();
     }
@@ -343,43 +477,54 @@ __device__ inline Fr block_round_challenge(TsShared& S, DevState* st, const Fr* 
         }
         S.tmp[k] = c;
     }
-    block_absorb1(S, 'g', npts - 1, true);
-    // challenge hashes on the schedules prepared during the absorb: lanes 0, 1 (the two
-    // halves of the element), 2 (the block that extends the stream)
-    if (tid < 3) {
-        sha::Words8 h;
+    const int prep = block_absorb1(S, 'g', npts - 1, true);
+    Fr v;
+    if (prep >= 0) {
+        // challenge hashes on the schedules prepared during the absorb: lanes 0, 1 (the two
+        // halves of the element), 2 (the block that extends the stream)
+        if (tid < 3) {
+            sha::Words8 h;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
-        const sha::Words8 ow = sha::rounds_lds(h, (sha::lds_u32_cptr)S.wk[ts_frame_blocks(npts - 1) + tid]);
-        if (tid < 2) {
-            Fr x;
+            for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
+            const sha::Words8 ow = sha::rounds_lds(h, (sha::lds_u32_cptr)S.wk[prep + tid]);
+            if (tid < 2) {
+                Fr x;
 #pragma unroll
-            for (int l = 0; l < 8; ++l) x.v[l] = sha::bswap32(ow.v[l]);
-            Fr m = fr_mul_ni(fr_const(tid ? frc::W3 : frc::R2), x);
+                for (int l = 0; l < 8; ++l) x.v[l] = sha::bswap32(ow.v[l]);
+                Fr m = fr_mul_ni(fr_const(tid ? frc::W3 : frc::R2), x);
 #pragma unroll
-            for (int l = 0; l < 8; ++l) S.dig[tid][l] = m.v[l];
-        } else {
+                for (int l = 0; l < 8; ++l) S.dig[tid][l] = m.v[l];
+            } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) S.dig[2][i] = ow.v[i];
+                for (int i = 0; i < 8; ++i) S.dig[2][i] = ow.v[i];
+            }
         }
-    }
-    __syncthreads();
-    Fr lo, hi;
+        __syncthreads();
+        Fr lo, hi;
 #pragma unroll
-    for (int l = 0; l < 8; ++l) {
-        lo.v[l] = S.dig[0][l];
-        hi.v[l] = S.dig[1][l];
+        for (int l = 0; l < 8; ++l) {
+            lo.v[l] = S.dig[0][l];
+            hi.v[l] = S.dig[1][l];
+        }
+        v = fr_add(lo, hi);   // every thread
+        if (tid < 8) S.state[tid] = S.dig[2][tid];
+        if (tid == 8) {
+            S.nblk += 1;
+            S.fill = 0;
+        }
+        if (tid == 128) {
+            Fr plain = fr_from_mont_ni(v);
+            uint32_t* le = (uint32_t*)(st->chal_le + 32 * (size_t)chal_idx);
+#pragma unroll
+            for (int l = 0; l < 8; ++l) le[l] = plain.v[l];
+        }
+    } else {
+        // the unfinished block is too full for single closing blocks (a round that follows
+        // other frames without a draw in between): the general draw
+        block_challenges(S, st, chal_idx, 1);
+        v = S.v;
     }
-    const Fr v = fr_add(lo, hi);   // every thread
-    if (tid < 8) S.state[tid] = S.dig[2][tid];
-    if (tid == 8) S.nblk += 1;
     if (tid == 0) st->chal[chal_idx] = v;
-    if (tid == 128) {
-        Fr plain = fr_from_mont_ni(v);
-        uint32_t* le = (uint32_t*)(st->chal_le + 32 * (size_t)chal_idx);
-#pragma unroll
-        for (int l = 0; l < 8; ++l) le[l] = plain.v[l];
-    }
     return v;
 }
 

@@ -477,32 +477,17 @@ int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, void* work_mem, 
 
 // ---- transcript-only kernels -----------------------------------------------------
 struct FramesArg {
-    uint32_t words[ZK_PEND_CAP / 4];   // whole blocks, big-endian words
-    int nblocks;
+    uint32_t words[ZK_PEND_CAP / 4];   // the frames' bytes, four per word, first byte in the top bits
+    uint32_t len;                      // bytes
 };
 
 // absorbs host-known frames (protocol headers), then draws `count` challenges
 __global__ __launch_bounds__(ZK_BLOCK) void k_frames_draw(DevState* st, FramesArg f, int base, int count) {
     __shared__ TsShared S;
     block_ts_load(S, st);
-    if (f.nblocks > 0) {
-        if (threadIdx.x < (unsigned)f.nblocks) {
-            sha::Words16 w;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) w.v[i] = f.words[16 * threadIdx.x + i];
-            sha::schedule_wk_lds(w, (sha::lds_u32_ptr)S.wk[threadIdx.x]);
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            sha::Words8 h;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) h.v[i] = S.state[i];
-            for (int blk = 0; blk < f.nblocks; ++blk) h = sha::rounds_lds(h, (sha::lds_u32_cptr)S.wk[blk]);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) S.state[i] = h.v[i];
-            S.nblk += (uint64_t)f.nblocks;
-        }
-        __syncthreads();
+    if (f.len > 0) {
+        auto frame = [&](uint32_t q) -> uint32_t { return (f.words[q >> 2] >> (24 - 8 * (q & 3))) & 0xffu; };
+        block_append(S, f.len, frame, false);
     }
     block_challenges(S, st, base, count);
     block_ts_store(S, st);
@@ -512,28 +497,24 @@ void zk_absorb_words(zkdl_ctx* ctx, const char* label, const uint32_t* words, in
     uint32_t ll = 0;
     while (label[ll] && ll < ts::MAX_LABEL) ++ll;
     const uint32_t len = 1 + ll + 8 + 4 * (uint32_t)n;
-    const uint32_t padded = (len + 63) / 64 * 64;
-    if (ctx->pend_len + padded > (uint32_t)ZK_PEND_CAP) zk_flush_frames(ctx);
+    if (ctx->pend_len + len > (uint32_t)ZK_PEND_CAP) zk_flush_frames(ctx);
     uint8_t* p = ctx->pend + ctx->pend_len;
-    memset(p, 0, padded);
     *p++ = (uint8_t)ll;
     for (uint32_t i = 0; i < ll; ++i) *p++ = (uint8_t)label[i];
     const uint64_t dl = 4 * (uint64_t)n;
     for (int i = 0; i < 8; ++i) *p++ = (uint8_t)(dl >> (8 * i));
     for (int i = 0; i < n; ++i)
         for (int b = 0; b < 4; ++b) *p++ = (uint8_t)(words[i] >> (8 * b));
-    ctx->pend_len += padded;
+    ctx->pend_len += len;
 }
 
 void zk_launch_draw(zkdl_ctx* ctx, int chal_base, int count) {
     if (count <= 0 && ctx->pend_len == 0) return;
-    static_assert(ZK_PEND_CAP / 64 <= TS_MAX_FRAME_BLOCKS + 3, "one schedule row per pending block");
+    static_assert((ZK_PEND_CAP + 63) / 64 <= TS_MAX_BLOCKS, "one schedule row per block an append completes");
     FramesArg f;
-    f.nblocks = (int)(ctx->pend_len / 64);
-    for (uint32_t i = 0; i < ctx->pend_len / 4; ++i) {
-        const uint8_t* p = ctx->pend + 4 * i;
-        f.words[i] = ((uint32_t)p[0] << 24) | ((uint32_t)p[1] << 16) | ((uint32_t)p[2] << 8) | p[3];
-    }
+    f.len = ctx->pend_len;
+    for (uint32_t i = 0; i < (uint32_t)ZK_PEND_CAP / 4; ++i) f.words[i] = 0;
+    for (uint32_t i = 0; i < ctx->pend_len; ++i) f.words[i >> 2] |= (uint32_t)ctx->pend[i] << (24 - 8 * (i & 3));
     ctx->pend_len = 0;
     hipLaunchKernelGGL(k_frames_draw, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, f, chal_base,
                        count > 0 ? count : 0);

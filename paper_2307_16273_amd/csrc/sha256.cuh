@@ -3,18 +3,21 @@
 //
 // The paper's verifier sends a uniform field element after each round
 // polynomial (App. B); the transcript replaces that message by a hash.  The
-// transcript is one byte stream, always a whole number of 64-byte blocks:
-//   stream_0         = "zkdl-mi355x/v2" zero-padded to 56 bytes || u64le(seed)
-//   absorb(label, m) : stream <- stream || pad64(u8(|label|) || label || u64le(|m|) || m)
+// transcript is one byte stream:
+//   stream_0         = "zkdl-mi355x/v3" zero-padded to 56 bytes || u64le(seed)
+//   absorb(label, m) : stream <- stream || u8(|label|) || label || u64le(|m|) || m
 //   challenges(n)    : for i < n: d0 = SHA256(stream || 0xF0 || u32le(i)),
 //                      d1 = SHA256(stream || 0xF1 || u32le(i)), c_i = int_le(d0 || d1) mod r;
-//                      then stream <- stream || 0xF2 || 63 zero bytes.  challenge() = challenges(1)[0].
+//                      then stream <- stream || 0xF2 || zero bytes up to the next multiple of 64.
+//                      challenge() = challenges(1)[0].
 //   digest()         = SHA256(stream)
-// The state is the SHA-256 chaining value after the last block and the block count:
-// an absorb is one compression per 64 message bytes, every hash of a draw is one
-// compression from the chaining value (its block: tag, index, padding, bit length), and
-// the message schedules of all of these do not depend on the chaining value, so they
-// are computed beforehand, in other lanes than the one that runs the rounds.
+// The state is the SHA-256 chaining value after the last whole block, the block count and the
+// bytes of the unfinished block.  After a draw the stream is block-aligned, so a sumcheck round
+// (a 106-byte frame, then one challenge) is one compression for the frame's first 64 bytes and
+// then three independent ones from that chaining value: the two hashes of the draw (last block:
+// the other 42 bytes, tag, index, padding, bit length) and the block that extends the stream.
+// No message schedule depends on a chaining value, so they are all computed beforehand, in
+// other lanes than the one that runs the rounds.
 #pragma once
 #include <stdint.h>
 #include <hip/hip_runtime.h>
@@ -194,23 +197,6 @@ static __device__ __noinline__ Words8 rounds_lds(Words8 hin, lds_u32_cptr wk) {
     return o;
 }
 
-// The block that closes SHA256(stream || tag || u32le(idx)) for a stream of nblk whole
-// blocks (tag 0xF0 / 0xF1), or the block 0xF2 || zeros appended after a draw (tag 0xF2).
-__device__ inline Words16 draw_block_words(uint32_t tag, uint32_t idx, uint64_t nblk) {
-    Words16 w;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) w.v[i] = 0;
-    if (tag == 0xF2u) {
-        w.v[0] = 0xF2000000u;
-    } else {
-        w.v[0] = (tag << 24) | ((idx & 0xffu) << 16) | (((idx >> 8) & 0xffu) << 8) | ((idx >> 16) & 0xffu);
-        w.v[1] = ((idx >> 24) << 24) | 0x00800000u;
-        const uint64_t bits = nblk * 512u + 40u;
-        w.v[14] = (uint32_t)(bits >> 32);
-        w.v[15] = (uint32_t)bits;
-    }
-    return w;
-}
 #endif
 
 SHA_HD uint32_t bswap32(uint32_t x) {
@@ -239,21 +225,32 @@ namespace ts {
 
 constexpr uint32_t MAX_LABEL = 32;
 
-// chaining value after the last whole block of the stream, and the number of blocks
+// chaining value after the last whole block of the stream, the number of whole blocks, and
+// the bytes of the unfinished block
 struct State {
     uint32_t h[8];
     uint64_t nblk;
+    uint8_t buf[64];
+    uint32_t fill;
 };
 
-SHA_HD void push_block(State& s, const uint8_t blk[64]) {
+SHA_HD void compress_bytes(uint32_t h[8], const uint8_t blk[64]) {
     uint32_t w[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const uint8_t* p = blk + 4 * i;
         w[i] = ((uint32_t)p[0] << 24) | ((uint32_t)p[1] << 16) | ((uint32_t)p[2] << 8) | p[3];
     }
-    sha::compress(s.h, w);
-    s.nblk += 1;
+    sha::compress(h, w);
+}
+
+SHA_HD void push_byte(State& s, uint8_t b) {
+    s.buf[s.fill++] = b;
+    if (s.fill == 64) {
+        compress_bytes(s.h, s.buf);
+        s.nblk += 1;
+        s.fill = 0;
+    }
 }
 
 SHA_HD void init(State& s, uint64_t seed) {
@@ -261,42 +258,28 @@ SHA_HD void init(State& s, uint64_t seed) {
                             0x510e527f, 0x9b05688c, 0x1f83d9ab, 0x5be0cd19};
     for (int i = 0; i < 8; ++i) s.h[i] = iv[i];
     s.nblk = 0;
-    const char dom[] = "zkdl-mi355x/v2";
-    uint8_t blk[64];
-    for (int i = 0; i < 64; ++i) blk[i] = 0;
-    for (int i = 0; i < (int)sizeof(dom) - 1; ++i) blk[i] = (uint8_t)dom[i];
-    for (int i = 0; i < 8; ++i) blk[56 + i] = (uint8_t)(seed >> (8 * i));
-    push_block(s, blk);
+    s.fill = 0;
+    const char dom[] = "zkdl-mi355x/v3";
+    for (int i = 0; i < 56; ++i) push_byte(s, i < (int)sizeof(dom) - 1 ? (uint8_t)dom[i] : 0);
+    for (int i = 0; i < 8; ++i) push_byte(s, (uint8_t)(seed >> (8 * i)));
 }
 
-// stream <- stream || pad64(u8(label_len) || label || u64le(n) || data), block by block
+// stream <- stream || u8(label_len) || label || u64le(n) || data
 SHA_HD void absorb(State& s, const char* label, uint32_t label_len, const uint8_t* data, uint64_t n) {
-    uint8_t blk[64];
-    uint32_t p = 0;
-    blk[p++] = (uint8_t)label_len;
-    for (uint32_t i = 0; i < label_len; ++i) blk[p++] = (uint8_t)label[i];   // label_len <= 32
-    for (int i = 0; i < 8; ++i) blk[p++] = (uint8_t)(n >> (8 * i));
-    for (uint64_t i = 0; i < n; ++i) {
-        if (p == 64) {
-            push_block(s, blk);
-            p = 0;
-        }
-        blk[p++] = data[i];
-    }
-    while (p < 64) blk[p++] = 0;
-    push_block(s, blk);
+    push_byte(s, (uint8_t)label_len);
+    for (uint32_t i = 0; i < label_len; ++i) push_byte(s, (uint8_t)label[i]);
+    for (int i = 0; i < 8; ++i) push_byte(s, (uint8_t)(n >> (8 * i)));
+    for (uint64_t i = 0; i < n; ++i) push_byte(s, data[i]);
 }
 
-// SHA256(stream || tail), tail of at most 55 bytes, as big-endian words
+// SHA256(stream || tail), tail of at most 8 bytes, as big-endian words
 SHA_HD void tail_digest_w(const State& s, const uint8_t* tail, uint32_t tail_len, uint32_t out[8]) {
-    uint8_t blk[64];
-    for (int i = 0; i < 64; ++i) blk[i] = 0;
-    for (uint32_t i = 0; i < tail_len; ++i) blk[i] = tail[i];
-    blk[tail_len] = 0x80;
-    const uint64_t bits = (s.nblk * 64 + tail_len) * 8;
-    for (int i = 0; i < 8; ++i) blk[63 - i] = (uint8_t)(bits >> (8 * i));
     State f = s;
-    push_block(f, blk);
+    const uint64_t bits = (s.nblk * 64 + s.fill + tail_len) * 8;
+    for (uint32_t i = 0; i < tail_len; ++i) push_byte(f, tail[i]);
+    push_byte(f, 0x80);
+    while (f.fill != 56) push_byte(f, 0);
+    for (int i = 7; i >= 0; --i) push_byte(f, (uint8_t)(bits >> (8 * i)));
     for (int i = 0; i < 8; ++i) out[i] = f.h[i];
 }
 
@@ -317,12 +300,10 @@ SHA_HD Fr challenge_elem(const State& s, uint32_t idx) {
     return fr_from_wide(lo, hi);
 }
 
-// the stream extension that follows a draw
+// the stream extension that follows a draw: 0xF2, then zeros up to the block boundary
 SHA_HD void ratchet(State& s) {
-    uint8_t blk[64];
-    for (int i = 0; i < 64; ++i) blk[i] = 0;
-    blk[0] = 0xF2;
-    push_block(s, blk);
+    push_byte(s, 0xF2);
+    while (s.fill != 0) push_byte(s, 0);
 }
 
 // canonical little-endian bytes of a Montgomery-form element

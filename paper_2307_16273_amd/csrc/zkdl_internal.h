@@ -15,7 +15,8 @@ constexpr int ZK_PROOF_CAP = 1 << 17;      // proof bytes one call may write
 constexpr int ZK_MAX_PART_BLOCKS = 1024;   // partial-sum slots of a round kernel
 constexpr int ZK_MAX_EVALS = 4;            // evaluations per round polynomial (degree <= 3)
 constexpr int ZK_BLOCK = 256;
-constexpr int ZK_PEND_CAP = 512;         // host-known transcript frames waiting for the next transcript kernel
+constexpr int ZK_PEND_CAP = 448;         // bytes of host-known transcript frames waiting for the next transcript kernel
+constexpr int ZK_STATE_HEAD = 128;       // bytes at the start of DevState that a call sets from the host
 
 // Device-resident state of the call in flight.
 struct DevState {
@@ -24,7 +25,9 @@ struct DevState {
     uint32_t ts_nblk[2];    // transcript: number of 64-byte blocks in the stream (low, high word)
     uint32_t lag_npts;      // != 0: claim is owed, claim = g(chal[lag_chal]) with the coefficients lag[]
     uint32_t lag_chal;
-    uint32_t pad0[3];
+    uint32_t ts_fill;       // transcript: bytes of the unfinished block
+    uint32_t pad0[2];
+    uint32_t ts_buf[16];    // transcript: the unfinished block, big-endian words, zero beyond ts_fill
     Fr claim;               // claim of the running sumcheck (Montgomery); current if lag_npts == 0
     Fr lag[4];              // Lagrange coefficients of the last round polynomial
     Fr inv2, inv6;          // constants of the Lagrange formulas
@@ -63,7 +66,7 @@ struct zkdl_ctx {
     int n_chal;
     size_t proof_len;
     // transcript frames known on the host (protocol headers) that the next transcript
-    // kernel absorbs before anything else; whole 64-byte blocks
+    // kernel absorbs before anything else
     uint8_t pend[ZK_PEND_CAP];
     uint32_t pend_len;
     // optional per-kernel-class timing with HIP events on the context's stream

@@ -79,18 +79,18 @@ def test_transcript_format():
         "ba7816bf8f01cfea414140de5dae2223b00361a396177a9cb410ff61f20015ad"
     # every value is a one-shot hash of an explicitly written byte stream
     t = Transcript(9)
-    stream = b"zkdl-mi355x/v2" + b"\0" * 42 + struct.pack("<Q", 9)
+    stream = b"zkdl-mi355x/v3" + b"\0" * 42 + struct.pack("<Q", 9)
     assert len(stream) == 64 and t.digest() == hashlib.sha256(stream).digest()
     t.absorb(b"g", b"\x01\x02")
-    stream += b"\x01g" + struct.pack("<Q", 2) + b"\x01\x02" + b"\0" * 52
-    assert len(stream) == 128 and t.digest() == hashlib.sha256(stream).digest()
+    stream += b"\x01g" + struct.pack("<Q", 2) + b"\x01\x02"
+    assert len(stream) == 76 and t.digest() == hashlib.sha256(stream).digest()
     c = t.challenge()
     z4 = struct.pack("<I", 0)
     wide = hashlib.sha256(stream + b"\xf0" + z4).digest() + hashlib.sha256(stream + b"\xf1" + z4).digest()
     assert c == int.from_bytes(wide, "little") % R_MOD
     s1 = stream
-    stream += b"\xf2" + b"\0" * 63
-    assert t.digest() == hashlib.sha256(stream).digest()
+    stream += b"\xf2" + b"\0" * 51      # a draw closes the block
+    assert len(stream) == 128 and t.digest() == hashlib.sha256(stream).digest()
     assert t.challenge() != c
     # a vector draw: index-derived elements, one stream extension
     t2 = Transcript(9)
@@ -101,37 +101,48 @@ def test_transcript_format():
     wide = hashlib.sha256(s1 + b"\xf0" + i2).digest() + hashlib.sha256(s1 + b"\xf1" + i2).digest()
     assert vec[2] == int.from_bytes(wide, "little") % R_MOD
     assert t2.challenges_vec(0) == [] and t2.digest() == hashlib.sha256(stream).digest()
-    # frames longer than a block, a frame that fills its last block exactly, the longest label
+    # frames are appended without padding, whatever their length; a draw on an aligned stream
+    # appends a whole block
     t3 = Transcript(1)
-    s3 = b"zkdl-mi355x/v2" + b"\0" * 42 + struct.pack("<Q", 1)
+    s3 = b"zkdl-mi355x/v3" + b"\0" * 42 + struct.pack("<Q", 1)
     for label, data in ((b"f", bytes(range(96))), (b"x", bytes(54)), (b"y" * 32, bytes(200)), (b"", b"")):
         t3.absorb(label, data)
-        frame = bytes([len(label)]) + label + struct.pack("<Q", len(data)) + data
-        s3 += frame + b"\0" * (-len(frame) % 64)
-        assert len(s3) % 64 == 0 and t3.digest() == hashlib.sha256(s3).digest()
-    assert len(b"\x01x" + struct.pack("<Q", 54) + bytes(54)) == 64     # the exact-fit case above
+        s3 += bytes([len(label)]) + label + struct.pack("<Q", len(data)) + data
+        assert t3.digest() == hashlib.sha256(s3).digest()
+    t3.challenge()
+    s3 += b"\xf2" + b"\0" * (-(len(s3) + 1) % 64)
+    assert len(s3) % 64 == 0 and t3.digest() == hashlib.sha256(s3).digest()
+    t3.challenge()
+    s3 += b"\xf2" + b"\0" * 63
+    assert t3.digest() == hashlib.sha256(s3).digest()
 
 
-def test_transcript_draw_is_one_compression_from_the_chaining_value():
-    """The property the format is built for: the stream is block-aligned, so a challenge hash
-    is a single compression applied to the chaining value after the last absorbed block."""
+def test_transcript_round_step_is_two_compressions_deep():
+    """The property the format is built for: after a draw the stream is block-aligned, so
+    absorbing a round's 106-byte frame and drawing the challenge is one compression for the
+    frame's first 64 bytes and then independent single compressions from that chaining value."""
     assert b"".join(struct.pack(">I", x) for x in _sha256_compress(
         _SHA256_IV, b"abc\x80" + b"\0" * 52 + struct.pack(">Q", 24))) == hashlib.sha256(b"abc").digest()
     t = Transcript(5)
+    t.challenge()                      # leaves the stream aligned: 128 bytes
     t.absorb_fr(b"g", [3, 4, 5])
-    blocks = b"zkdl-mi355x/v2" + b"\0" * 42 + struct.pack("<Q", 5)
+    head = b"zkdl-mi355x/v3" + b"\0" * 42 + struct.pack("<Q", 5) + b"\xf2" + b"\0" * 63
     frame = b"\x01g" + struct.pack("<Q", 96) + to_le(3) + to_le(4) + to_le(5)
-    blocks += frame + b"\0" * (128 - len(frame))
+    assert len(head) == 128 and len(frame) == 106
     h = _SHA256_IV
-    for off in range(0, len(blocks), 64):
-        h = _sha256_compress(h, blocks[off:off + 64])
+    for off in (0, 64):
+        h = _sha256_compress(h, head[off:off + 64])
+    h = _sha256_compress(h, frame[:64])                     # the one sequential compression
+    rest = frame[64:]                                       # 42 bytes
     halves = []
     for tag in (0xF0, 0xF1):
-        last = bytes([tag]) + struct.pack("<I", 0) + b"\x80" + b"\0" * 50 + struct.pack(">Q", 8 * (len(blocks) + 5))
+        last = rest + bytes([tag]) + struct.pack("<I", 0) + b"\x80"
+        last += b"\0" * (56 - len(last)) + struct.pack(">Q", 8 * (128 + 106 + 5))
+        assert len(last) == 64
         halves.append(b"".join(struct.pack(">I", x) for x in _sha256_compress(h, last)))
     assert t.challenge() == int.from_bytes(halves[0] + halves[1], "little") % R_MOD
-    h = _sha256_compress(h, b"\xf2" + b"\0" * 63)
-    fin = b"\x80" + b"\0" * 55 + struct.pack(">Q", 8 * (len(blocks) + 64))
+    h = _sha256_compress(h, rest + b"\xf2" + b"\0" * 21)
+    fin = b"\x80" + b"\0" * 55 + struct.pack(">Q", 8 * 256)
     assert t.digest() == b"".join(struct.pack(">I", x) for x in _sha256_compress(h, fin))
 
 

@@ -73,16 +73,16 @@ def test_product_sumcheck_transcript_stream_written_out():
     _, proof, vs = P.product_prove(tabs, ts)
 
     def frame(label, data):
-        f = bytes([len(label)]) + label + struct.pack("<Q", len(data)) + data
-        return f + b"\0" * (-len(f) % 64)
-    stream = b"zkdl-mi355x/v2" + b"\0" * 42 + struct.pack("<Q", 12)
+        return bytes([len(label)]) + label + struct.pack("<Q", len(data)) + data
+    stream = b"zkdl-mi355x/v3" + b"\0" * 42 + struct.pack("<Q", 12)
     stream += frame(b"sumcheck_product", struct.pack("<II", k, d))
     stream += frame(b"c", to_le(proof.claim0))
     for t, g in enumerate(proof.rounds):
         stream += frame(b"g", to_le(g[0]) + to_le(g[2]) + to_le(g[3]))
         halves = [hashlib.sha256(stream + bytes([tag]) + struct.pack("<I", 0)).digest() for tag in (0xF0, 0xF1)]
         assert vs[t] == int.from_bytes(halves[0] + halves[1], "little") % R_MOD
-        stream += b"\xf2" + b"\0" * 63
+        stream += b"\xf2"
+        stream += b"\0" * (-len(stream) % 64)
     stream += frame(b"f", b"".join(to_le(x) for x in proof.finals))
     assert ts.digest() == hashlib.sha256(stream).digest()
 
