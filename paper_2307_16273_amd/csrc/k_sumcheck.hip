@@ -254,8 +254,15 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_tail(ScTailArgs a) {
     // the claim of the round before may still be owed; it is first read after a barrier
     if (wave == 3) wave_resolve_claim(st);
     int el_cur = -1;   // buffer of `el` that holds the current tables; -1: they are in memory
+    bool owe = false;  // the claim g(v_owe) of the round before is still to be evaluated
+    Fr v_owe = fr_zero();
     for (int t = 0; t < a.rounds; ++t) {
         if (m > 64) {
+            if (owe && wave == 3) {
+                const Fr c = wave_lagrange(S.tmp, K + 1, v_owe);
+                if (lane == 0) st->claim = c;
+            }
+            owe = false;
             F9 acc[K + 1];
 #pragma unroll
             for (int x = 0; x <= K; ++x) acc[x] = f9_zero();
@@ -303,6 +310,11 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_tail(ScTailArgs a) {
                 }
             }
             __syncthreads();
+            if (owe && wave == 3) {   // between the two barriers the other waves multiply
+                const Fr c = wave_lagrange(S.tmp, K + 1, v_owe);
+                if (lane == 0) st->claim = c;
+            }
+            owe = false;
             F9 prod = f9_zero();
             if (wave < K && lane < mi) {
 #pragma unroll
@@ -333,12 +345,10 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_tail(ScTailArgs a) {
         __syncthreads();
         Fr vr = block_round_challenge(S, st, g, K + 1, a.rounds_off + (uint32_t)t * (K + 1) * 32,
                                       a.first_chal + 1 + t);
-        // the next claim is evaluated by wave 3 while the others fold with the new challenge;
-        // it is read after the barriers of the next round's sums
-        if (wave == 3) {
-            const Fr c = wave_lagrange(S.tmp, K + 1, vr);
-            if (lane == 0) st->claim = c;
-        }
+        // the next claim is evaluated by wave 3 next to the following round's work; it is
+        // read after the barriers of that round's sums
+        owe = true;
+        v_owe = vr;
         v = fr_unpack(vr);
         m >>= 1;
     }
