@@ -365,52 +365,63 @@ __device__ __forceinline__ FrTab aux_col(const BinArgs& a, int k, int j) {
     return t;
 }
 
-// sum of beta_J(j) over the set bits of `mask`
-__device__ __forceinline__ Fr masked_sum(const Fr* bJ, uint64_t mask, int nbits) {
-    Fr s = fr_zero();
-    for (int j = 0; j < nbits; ++j)
-        if ((mask >> j) & 1) s = fr_add(s, bJ[j]);
-    return s;
+// sum of beta_J (lazy limbs, LDS) over the set bits of mask; normal on return
+__device__ __forceinline__ F9 masked_sum9(const F9* sbj, uint64_t mask) {
+    F9 s = f9_zero();
+    int pending = 0;
+    while (mask) {
+        const int j = __builtin_ctzll(mask);
+        mask &= mask - 1;
+        s = f9_add(s, sbj[j]);
+        if (++pending == 4) {
+            pending = 0;
+            s = f9_norm(s);
+        }
+    }
+    return f9_norm(s);
 }
 
 // Round 0: both halves are bits, a(x)^2 - a(x) = (x^2 - x) [lo != hi]; contributes
 // 2 beta_I(2, i') C(i') at x = 2 and 6 beta_I(3, i') C(i') at x = 3,
 // C = sum_j beta_J(j) ([z bits differ] + r' [g bits differ]).
 __device__ __forceinline__ void bin0_body(const BinArgs& a, const unsigned bx, const unsigned gx) {
-    __shared__ uint32_t red[64];
-    __shared__ Fr sbj[64];
-    if (threadIdx.x < 64) sbj[threadIdx.x] = threadIdx.x < (unsigned)a.nbits ? a.bJ[threadIdx.x] : fr_zero();
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    __shared__ F9 sbj[2][64];   // beta_J, and r' beta_J for the second slice
+    const int tid = threadIdx.x;
+    if (tid < 128) {
+        const int j = tid & 63, k = tid >> 6;
+        F9 x = f9_zero();
+        if (j < a.nbits) x = fr_unpack(k == 0 ? a.bJ[j] : fr_mul(*a.rp, a.bJ[j]));
+        sbj[k][j] = x;
+    }
     __syncthreads();
-    Fr acc2 = fr_zero(), acc3 = fr_zero();
+    F9 acc[2];
+    acc[0] = f9_zero();
+    acc[1] = f9_zero();
     const uint64_t m = a.m;
     const uint64_t keep = a.nbits >= 64 ? ~(uint64_t)0 : (((uint64_t)1 << a.nbits) - 1);
-    Fr rp = *a.rp;
-    for (uint64_t b = bx * (uint64_t)blockDim.x + threadIdx.x; b < m;
-         b += (uint64_t)gx * blockDim.x) {
-        uint64_t dz = ((uint64_t)a.z[b] ^ (uint64_t)a.z[b + m]) & keep;
-        Fr c = masked_sum(sbj, dz, a.nbits);
+    for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
+        const uint64_t dz = ((uint64_t)a.z[b] ^ (uint64_t)a.z[b + m]) & keep;
+        F9 c = masked_sum9(sbj[0], dz);                      // normal, below 64 r
         if (a.has_ga) {
-            uint64_t dg = ((uint64_t)a.ga[b] ^ (uint64_t)a.ga[b + m]) & keep;
-            c = fr_add(c, fr_mul(rp, masked_sum(sbj, dg, a.nbits)));
+            const uint64_t dg = ((uint64_t)a.ga[b] ^ (uint64_t)a.ga[b + m]) & keep;
+            c = f9_add(c, masked_sum9(sbj[1], dg));          // limbs below 2^30
         }
-        // round 0: the table is as built, fully reduced
-        Fr lo = fr_pack(f9tab_ld(a.bI, b)), hi = fr_pack(f9tab_ld(a.bI, b + m));
-        Fr d = fr_sub(hi, lo);
-        Fr b2 = fr_add(hi, d), b3 = fr_add(b2, d);
-        Fr c2 = fr_dbl(c);                       // (x^2 - x) = 2 at x = 2
-        Fr c6 = fr_add(fr_dbl(c2), c2);          // 6 at x = 3
-        acc2 = fr_add(acc2, fr_mul(b2, c2));
-        acc3 = fr_add(acc3, fr_mul(b3, c6));
+        // round 0: the table is as built, fully reduced; line at x = 2, 3, normal
+        const F9 lo = f9tab_ld(a.bI, b), hi = f9tab_ld(a.bI, b + m);
+        const F9 dn = f9_norm(f9_sub(hi, lo));
+        const F9 b2 = f9_norm(f9_add(hi, dn)), b3 = f9_norm(f9_add(b2, dn));
+        acc[0] = f9_norm_reduce(f9_add(acc[0], f9_mul(b2, c)));
+        acc[1] = f9_norm_reduce(f9_add(acc[1], f9_mul(b3, c)));
     }
-    Fr s2 = block_sum(acc2, red);
-    Fr s3 = block_sum(acc3, red);
-    if (threadIdx.x == 0) {
-        Fr* p = a.part + (uint64_t)bx * 4;
-        p[0] = fr_zero();
-        p[1] = fr_zero();
-        p[2] = s2;
-        p[3] = s3;
-    }
+    // (x^2 - x) = 2 at x = 2 and 6 at x = 3
+    acc[0] = f9_norm_reduce(f9_add(acc[0], acc[0]));
+    const F9 a3 = f9_add(acc[1], acc[1]);
+    acc[1] = f9_norm_reduce(f9_add(f9_add(a3, a3), a3));     // limbs below 6 * 2^29
+    const Fr s = block_sum_lazy<2>(acc, red);
+    Fr* p = a.part + (uint64_t)bx * 4;
+    if (tid < 2) p[2 + tid] = s;
+    else if (tid < 4) p[tid - 2] = fr_zero();
 }
 
 // ---- rounds >= 1 work on field elements; the first two challenges are bound by table look-up ----
@@ -434,22 +445,6 @@ __device__ __forceinline__ F9Tab aux_col9(const BinArgs& a, int k, int j) {
 
 __device__ __forceinline__ Fr bit_pair_value(int code, const Fr& v, const Fr& one) {
     return code == 0 ? fr_zero() : code == 3 ? one : code == 2 ? v : fr_sub(one, v);
-}
-
-// sum of beta_J (lazy limbs, LDS) over the set bits of mask; normal on return
-__device__ __forceinline__ F9 masked_sum9(const F9* sbj, uint64_t mask) {
-    F9 s = f9_zero();
-    int pending = 0;
-    while (mask) {
-        const int j = __builtin_ctzll(mask);
-        mask &= mask - 1;
-        s = f9_add(s, sbj[j]);
-        if (++pending == 4) {
-            pending = 0;
-            s = f9_norm(s);
-        }
-    }
-    return f9_norm(s);
 }
 
 // beta_I in rounds t >= 1: the source still has the entries for both values of the previous
@@ -496,38 +491,44 @@ __device__ __forceinline__ void bin1_body(const BinArgs& a, const unsigned bx, c
 #pragma unroll
     for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
     for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
-        F9 acc[3];
+        // sum over the combinations of Q_x[c] S_c as 64-bit columns: one reduction per (i'', x)
+        uint64_t cols[3][17];
 #pragma unroll
-        for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
+        for (int x = 0; x < 3; ++x)
+#pragma unroll
+            for (int c = 0; c < 17; ++c) cols[x][c] = 0;
         int pending = 0;
         for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
             const int64_t* src = k == 0 ? a.z : a.ga;
             // (x0, x1): w00 = (0,0), w01 = (0,1), w10 = (1,0), w11 = (1,1)
             const uint64_t w00 = (uint64_t)src[b], w01 = (uint64_t)src[b + m];
             const uint64_t w10 = (uint64_t)src[b + 2 * m], w11 = (uint64_t)src[b + 3 * m];
-            for (int c = 0; c < 16; ++c) {
+            for (int c = 1; c < 15; ++c) {   // q = 0 for c = 0, 15: both entries are the same bit
                 // lo entry (x1 = 0) interpolates bits (w00, w10); hi entry (x1 = 1) bits (w01, w11)
                 uint64_t mask = keep;
                 mask &= (c & 1) ? w00 : ~w00;
                 mask &= (c & 2) ? w10 : ~w10;
                 mask &= (c & 4) ? w01 : ~w01;
                 mask &= (c & 8) ? w11 : ~w11;
-                if (mask == 0 || c == 0 || c == 15) continue;   // q = 0 when both entries are equal bits
-                const F9 s = masked_sum9(sbj, mask);             // value < 48 r, normal
+                if (mask == 0) continue;
+                const F9 s = masked_sum9(sbj, mask);             // value < 64 r, normal
 #pragma unroll
-                for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(qx[k][x][c], s));
-                if (++pending == 2) {
+                for (int x = 0; x < 3; ++x) f9_cols_mac(cols[x], qx[k][x][c], s);
+                if (++pending == 4) {
                     pending = 0;
 #pragma unroll
-                    for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
+                    for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
                 }
             }
         }
         F9 bi[3];
         beta_line_fold(a, b, m, vprev9, bi);
 #pragma unroll
-        for (int x = 0; x < 3; ++x)
-            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_norm_reduce(acc[x]))));
+        for (int x = 0; x < 3; ++x) {
+            // at most 28 products below 64 r^2 each: the reduced sum is below 27 r, normal
+            f9_cols_norm<17>(cols[x]);
+            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_redc(cols[x]))));
+        }
     }
     {
         const Fr s = block_sum_lazy<3>(tot, red);

@@ -101,7 +101,7 @@ def test_mle_partial_eval(lib, ctx, shape, lo, hi, kind):
     assert out.download() == array_to_le(expect)
 
 
-@pytest.mark.parametrize("k,d", [(3, 0), (3, 1), (3, 2), (1, 5), (2, 9), (3, 10), (3, 14)])
+@pytest.mark.parametrize("k,d", [(3, 0), (3, 1), (3, 2), (1, 5), (2, 9), (3, 10), (1, 11), (2, 12), (3, 14)])
 def test_sumcheck_product(lib, ctx, k, d):
     say(f"sumcheck_product K={k} d={d}")
     n = 1 << d
