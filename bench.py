@@ -156,7 +156,24 @@ def main():
                    "partial_eval_elems_per_s": side * side / pe_med},
         "roofline": roofline,
     }
+    # fr_tensor_upload, reported on its own: 2^24 canonical Fr from host memory (PCIe copy +
+    # conversion to Montgomery limb planes), and the conversion alone from a device buffer
+    raw = uniform_fr_limbs(rng, n)
+    up_med, _ = timed(lambda: zk.fr_tensor_upload(ctx, raw, (n,)).free(), 3)
+    out["config"]["upload_fr_host_elems_per_s"] = n / up_med
+    del raw
     if not args.no_aggregate:
+        # config 1: one FC layer 16 x 256 x 256 and its ReLU (forward only); latency-dominated
+        from workloads import fc_relu_layer
+        lay = fc_relu_layer(CONFIG_SEED + 1)
+        x1 = zk.tensor_wrap_int(ctx, torch.from_numpy(lay["X"]).cuda(), (1, 16, 256))
+        w1 = zk.tensor_wrap_int(ctx, torch.from_numpy(lay["W"]).cuda(), (1, 256, 256))
+        z1 = torch.from_numpy(lay["Z"]).cuda().reshape(-1)
+        mm_med, _ = timed(lambda: zk.sumcheck_matmul(ctx, x1, w1, zk.Transcript(CONFIG_SEED + 1)), 5)
+        zr_med, _ = timed(lambda: zk.zkrelu_prove(ctx, z1, None, zk.Transcript(CONFIG_SEED + 1)), 5)
+        out["config"]["config1_matmul_us"] = 1e6 * mm_med
+        out["config"]["config1_zkrelu_us"] = 1e6 * zr_med
+        del x1, w1, z1
         wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)
         dw = {k: wit[k] for k in ("L", "B", "width", "T", "Q", "R")}
         for k in ("A", "W", "GZ", "Zr", "GA"):

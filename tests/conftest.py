@@ -20,3 +20,11 @@ def lib():
         pytest.skip("no GPU")
     import paper_2307_16273_amd as zk
     return zk
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    """One library context per test module."""
+    c = lib.Context(0)
+    yield c
+    c.close()

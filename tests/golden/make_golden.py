@@ -1,0 +1,77 @@
+"""Writes the stored expected proofs under tests/golden/ from the CPU oracle.
+
+Run from the repository root:  python tests/golden/make_golden.py
+Calls only `oracle/` and the seeded input generators in `workloads/`.  The files freeze
+the oracle's output (proof bytes, challenges, transcript digest) for three small
+instances, so that an unintended change of a byte format or of the oracle's arithmetic
+shows up as a diff; the paper prints no numeric worked example to store instead
+(its protocols are given symbolically: Sec. 2.2, Sec. 3.1, App. A, App. B).
+"""
+import json
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+
+from oracle import protocols as P                      # noqa: E402
+from oracle.field import fr_array, fr_array_from_le    # noqa: E402
+from oracle.transcript import Transcript               # noqa: E402
+from workloads import uniform_fr_limbs, fcnn_window    # noqa: E402
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def product_case():
+    """Product sumcheck (Sec. 2.2): K = 3 tables of 2^3 uniform field elements."""
+    rng = np.random.default_rng(20230716)
+    raws = [uniform_fr_limbs(rng, 8).tobytes() for _ in range(3)]
+    ts = Transcript(7)
+    buf, proof, vs = P.product_prove([fr_array_from_le(r, 8) for r in raws], ts)
+    return {"protocol": "sumcheck_product", "cite": "Sec. 2.2", "seed": 7, "tables_le_hex": [r.hex() for r in raws],
+            "proof_hex": buf.hex(), "challenges": [hex(v) for v in vs], "digest_hex": ts.digest().hex()}
+
+
+def matmul_case():
+    """Batched matrix product (Eq. exm-matmul-batched): N = 2, 2 x 4 times 4 x 2, small integers."""
+    rng = np.random.default_rng(20230717)
+    x0 = rng.integers(-50, 50, (2, 2, 4)).astype(np.int64)
+    x1 = rng.integers(-50, 50, (2, 4, 2)).astype(np.int64)
+    ts = Transcript(8)
+    buf, proof, _ = P.matmul_prove(fr_array(x0), [2, 2, 4], fr_array(x1), [2, 4, 2], ts)
+    return {"protocol": "sumcheck_matmul", "cite": "Eq. exm-matmul-batched", "seed": 8,
+            "x0": x0.reshape(-1).tolist(), "x0_shape": [2, 2, 4], "x1": x1.reshape(-1).tolist(), "x1_shape": [2, 4, 2],
+            "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
+
+
+def zkrelu_case():
+    """zkReLU (Sec. 3.1, App. A): D = 4, Q = 5, R = 3, with gradients."""
+    z = [77, -128, -1, 100]
+    ga = [-5, 127, 0, -64]
+    ts = Transcript(9)
+    buf, info = P.zkrelu_prove(z, ga, 5, 3, ts)
+    return {"protocol": "zkrelu_prove", "cite": "Sec. 3.1, App. A", "seed": 9, "Z": z, "GA": ga, "Q": 5, "R": 3,
+            "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
+
+
+def aggregate_case():
+    """Aggregated window (Sec. 5, Example FCNN): L = 2 layers of width 4, batch 2, 2 steps."""
+    wit = fcnn_window(2307162730 + 90, 2, 4, 2, 2)
+    ts = Transcript(10)
+    buf = P.aggregate_prove(wit, ts)
+    buf = buf[0] if isinstance(buf, tuple) else buf
+    return {"protocol": "aggregate_prove", "cite": "Sec. 5, Example FCNN", "seed": 10,
+            "workload": "fcnn_window(2307162730 + 90, n_layers=2, width=4, batch=2, steps=2)",
+            "proof_hex": bytes(buf).hex(), "challenges": [hex(v) for v in ts.challenges],
+            "digest_hex": ts.digest().hex()}
+
+
+if __name__ == "__main__":
+    for name, fn in (("product_k3_d3", product_case), ("matmul_n2_2x4x2", matmul_case),
+                     ("zkrelu_d4_q5_r3", zkrelu_case), ("aggregate_l2_w4_b2_t2", aggregate_case)):
+        with open(os.path.join(HERE, name + ".json"), "w") as f:
+            json.dump(fn(), f, indent=1)
+            f.write("\n")
+        print("wrote", name)

@@ -21,13 +21,6 @@ def say(msg):
     sys.stdout.flush()
 
 
-@pytest.fixture(scope="module")
-def ctx(lib):
-    c = lib.Context(0)
-    yield c
-    c.close()
-
-
 def rand_fr_bytes(seed, n):
     return uniform_fr_limbs(np.random.default_rng(seed), n).tobytes()
 
