@@ -345,6 +345,37 @@ def test_full_size_partial_eval_sampled(lib, ctx):
         assert int.from_bytes(out[32 * col:32 * col + 32], "little") == expect
 
 
+def test_full_size_microbench_byte_exact_against_c_tier(lib, ctx):
+    """The benchmark's own inputs and launch configuration (three tables of 2^24 uniform Fr,
+    the 4096 x 4096 matrix): proof bytes, challenges, transcript digest and every output of
+    the partial evaluation against the C tier of the oracle, which is pinned byte for byte
+    against the Python tier on small inputs (tests/test_oracle_c.py)."""
+    from oracle import c_oracle
+    say("full-size microbench, byte-exact against the C oracle tier")
+    d = 24
+    n = 1 << d
+    side = 1 << (d // 2)
+    rng = np.random.default_rng(CONFIG_SEED + 2)
+    raws = [uniform_fr_limbs(rng, n) for _ in range(3)]
+    mat = uniform_fr_limbs(rng, side * side)
+    point = [int.from_bytes(uniform_fr_limbs(rng, 1).tobytes(), "little") for _ in range(d // 2)]
+    tabs = [lib.fr_tensor_upload(ctx, r, (n,)) for r in raws]
+    tr = lib.Transcript(CONFIG_SEED + 2)
+    got = lib.sumcheck_product(ctx, tabs, tr)
+    for t in tabs:
+        t.free()
+    say("  C oracle: sumcheck")
+    proof, vs, digest = c_oracle.product_prove([r.tobytes() for r in raws], CONFIG_SEED + 2)
+    assert got["proof"] == proof
+    assert got["points"] == vs
+    assert tr.digest() == digest
+    del raws
+    tm = lib.fr_tensor_upload(ctx, mat, (side, side))
+    out = lib.mle_partial_eval(ctx, tm, 0, 1, point).download()
+    say("  C oracle: partial evaluation")
+    assert out == c_oracle.partial_eval(mat.tobytes(), 1, side, side, point)
+
+
 def test_config3_aggregate_by_properties(lib, ctx):
     """8 layers x 1024, batch 64 (the aggregate timed by the benchmark): the oracle's verifier
     accepts the proof and ends in the same transcript state; the forward family's claim on the
