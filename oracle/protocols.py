@@ -12,7 +12,7 @@ import numpy as np
 
 from .field import R_MOD, fr_array, to_le, from_le
 from .mle import ilog2, beta_table, mle_eval, partial_eval
-from .sumcheck import SumcheckProof, prove, verify_rounds
+from .sumcheck import SumcheckProof, prove, verify_rounds, lagrange_eval as _lagrange
 
 ZKRL_MAGIC = 0x4C524B5A   # bytes "ZKRL"
 ZKAG_MAGIC = 0x47414B5A   # bytes "ZKAG"
@@ -90,6 +90,108 @@ def matmul_verify(buf, n, d1, d2, d3, ts):
     assert fb == beta_point(w, vs[:len(w)]), "beta final is not beta~(w, v_n)"
     assert fb * f0 % R_MOD * f1 % R_MOD == claim, "final claim mismatch"
     return proof, dict(w=w, u0=u0, u1=u1, v=vs)
+
+
+# --------------------------------------------------------------------------
+# batched matrix product, optimized aggregated protocol (App. B, Protocol
+# tensor-op-aggr-optimized; Eqs. tensor-op-aggr-optimized, tensor-op-compressed-optimized)
+# --------------------------------------------------------------------------
+FT_MAGIC = 0x46534B5A   # "ZKSF"
+
+
+def matmul_ft_prove(x0, shape0, x1, shape1, ts):
+    """Y[n] = X0[n] X1[n] with the prover's messages of the optimized protocol.
+
+    Stack rounds t = 0..log N - 1: the prover sends, at x = 0, 1, 2,
+      f_t(x) = sum_{n'} beta~(w_[t+1:], n') sum_i X0~(v_<t, x, n', u0, i) X1~(v_<t, x, n', i, u1),
+    that is the round polynomial WITHOUT its factor beta~(w_t, x) (degree 2 instead of 3, and
+    no table for beta~(w, .) is ever folded); the verifier forms g_t(x) = beta~(w_t, x) f_t(x)
+    and checks g_t(0) + g_t(1) = claim, where claim is Y~(w, u0, u1) for t = 0 and
+    f_{t-1}(v_{t-1}) afterwards.  With the stack bound, the sumcheck of a single matrix
+    product follows on f_{n-1}(v_{n-1}) = sum_i X0~(v, u0, i) X1~(v, i, u1): K = 2, degree 2.
+
+    Transcript: header "sumcheck_matmul_ft" (N, D1, D2, D3); one draw (w, u0, u1); "c"
+    claim_0; per stack round "f" (f_t(0), f_t(1), f_t(2)) and a draw; then the product
+    sumcheck's rounds and finals (its claim_0 is not absorbed: the transcript fixes it).
+    Proof bytes: "ZKSF", u32 log N, u32 log D2, u32 0, claim_0, log N x 3 evaluations,
+    then the SC block of the second part (finals X0~(v_n, u0, v_i), X1~(v_n, v_i, u1)).
+    """
+    n, d1, d2 = shape0
+    n_, d2_, d3 = shape1
+    assert n == n_ and d2 == d2_
+    ts.absorb_u32(b"sumcheck_matmul_ft", [n, d1, d2, d3])
+    ln, l1, l2, l3 = ilog2(n), ilog2(d1), ilog2(d2), ilog2(d3)
+    pt = ts.challenges_vec(ln + l1 + l3)          # the point (w, u0, u1): one draw
+    w, u0, u1 = pt[:ln], pt[ln:ln + l1], pt[ln + l1:]
+    t0, _ = partial_eval(x0, [n, d1, d2], 1, 2, u0)          # [N, D2]
+    t1, _ = partial_eval(x1, [n, d2, d3], 2, 3, u1)          # [N, D2]
+    cur0 = np.asarray(t0, dtype=object).reshape(n, d2)
+    cur1 = np.asarray(t1, dtype=object).reshape(n, d2)
+    bw = beta_table(w)
+    claim0 = 0
+    for row in range(n):
+        claim0 = (claim0 + int(bw[row]) * int(np.sum(cur0[row] * cur1[row]) % R_MOD)) % R_MOD
+    ts.absorb_fr(b"c", [claim0])
+    claim = claim0
+    stack_rounds, vs = [], []
+    for t in range(ln):
+        half = cur0.shape[0] // 2
+        bs = beta_table(w[t + 1:])                           # beta~(w_[t+1:], n'), half entries
+        lo0, hi0, lo1, hi1 = cur0[:half], cur0[half:], cur1[:half], cur1[half:]
+        f = []
+        for x in range(3):
+            a = (lo0 + x * (hi0 - lo0)) % R_MOD
+            b = (lo1 + x * (hi1 - lo1)) % R_MOD
+            tot = 0
+            for row in range(half):
+                tot = (tot + int(bs[row]) * int(np.sum(a[row] * b[row]) % R_MOD)) % R_MOD
+            f.append(tot)
+        assert ((1 - w[t]) * f[0] + w[t] * f[1]) % R_MOD == claim, "stack round invariant broken"
+        ts.absorb_fr(b"f", f)
+        v = ts.challenge()
+        cur0 = (lo0 + v * (hi0 - lo0)) % R_MOD
+        cur1 = (lo1 + v * (hi1 - lo1)) % R_MOD
+        claim = _lagrange(f, v)
+        stack_rounds.append(f)
+        vs.append(v)
+    inner, vi = prove([cur0.reshape(-1), cur1.reshape(-1)], [(1, [0, 1])], 2, ts, absorb_claim=False)
+    assert inner.claim0 == claim, "the single-product sumcheck does not start at f_{n-1}(v_{n-1})"
+    out = [struct.pack("<IIII", FT_MAGIC, ln, l2, 0), to_le(claim0)]
+    for f in stack_rounds:
+        out.extend(to_le(x) for x in f)
+    out.append(inner.to_bytes())
+    info = dict(w=w, u0=u0, u1=u1, v=vs + vi, claim0=claim0, stack_rounds=stack_rounds, inner=inner)
+    return b"".join(out), info
+
+
+def matmul_ft_verify(buf, n, d1, d2, d3, ts):
+    """Replays the optimized protocol; returns (claim_0, finals (X0~, X1~), points).  The caller
+    checks claim_0 against Y~(w, u0, u1) and the finals against the committed tensors."""
+    magic, ln, l2, zero = struct.unpack_from("<IIII", buf, 0)
+    assert magic == FT_MAGIC and ln == ilog2(n) and l2 == ilog2(d2) and zero == 0
+    ts.absorb_u32(b"sumcheck_matmul_ft", [n, d1, d2, d3])
+    l1, l3 = ilog2(d1), ilog2(d3)
+    pt = ts.challenges_vec(ln + l1 + l3)
+    w, u0, u1 = pt[:ln], pt[ln:ln + l1], pt[ln + l1:]
+    off = 16
+    claim0 = from_le(buf[off:off + 32])
+    off += 32
+    ts.absorb_fr(b"c", [claim0])
+    claim, vs = claim0, []
+    for t in range(ln):
+        f = [from_le(buf[off + 32 * x:off + 32 * x + 32]) for x in range(3)]
+        off += 96
+        # g_t(x) = beta~(w_t, x) f_t(x): g_t(0) + g_t(1) = (1 - w_t) f_t(0) + w_t f_t(1)
+        assert ((1 - w[t]) * f[0] + w[t] * f[1]) % R_MOD == claim, "g(0)+g(1) != claim"
+        ts.absorb_fr(b"f", f)
+        v = ts.challenge()
+        claim = _lagrange(f, v)
+        vs.append(v)
+    inner, end = SumcheckProof.from_bytes(buf, off)
+    assert end == len(buf) and inner.n_finals == 2 and inner.degree == 2 and len(inner.rounds) == l2
+    last, vi = verify_rounds(inner, ts, absorb_claim=False, expected_claim0=claim)
+    assert inner.finals[0] * inner.finals[1] % R_MOD == last, "final claim mismatch"
+    return claim0, inner.finals, dict(w=w, u0=u0, u1=u1, v=vs + vi)
 
 
 # --------------------------------------------------------------------------

@@ -144,3 +144,68 @@ def test_hadamard_claim_is_mle_of_integer_product():
     tv = Transcript(6)
     P.hadamard_verify(buf, 5, tv)
     assert tv.digest() == ts.digest()
+
+
+# ---- optimized aggregated matrix-product protocol (App. B) ----
+@pytest.mark.parametrize("n,d1,d2,d3", [(4, 2, 4, 2), (1, 2, 8, 4), (8, 1, 2, 1), (2, 4, 1, 2)])
+def test_matmul_ft_against_definitions(n, d1, d2, d3):
+    """Every message of the optimized protocol against its definition written out with MLE
+    evaluations: claim_0 = Y~(w,u0,u1) for the integer product Y, f_t(x) as the double sum over
+    n' and i, the finals as evaluations of the inputs; and the verifier accepts."""
+    rng = np.random.default_rng(n * 100 + d2)
+    x0 = rng.integers(-9, 10, (n, d1, d2))
+    x1 = rng.integers(-9, 10, (n, d2, d3))
+    ts = Transcript(14)
+    buf, info = P.matmul_ft_prove(fr_array(x0), [n, d1, d2], fr_array(x1), [n, d2, d3], ts)
+    w, u0, u1, vs = info["w"], info["u0"], info["u1"], info["v"]
+    ln, l2 = len(w), d2.bit_length() - 1
+    y = np.einsum("nij,njk->nik", x0.astype(object), x1.astype(object))
+    assert info["claim0"] == mle_eval(fr_array(y), w + u0 + u1)
+    f0, f1 = fr_array(x0), fr_array(x1)
+    for t, f in enumerate(info["stack_rounds"]):
+        rest = ln - t - 1
+        for x in range(3):
+            acc = 0
+            for npr in itertools.product((0, 1), repeat=rest):
+                wt = 1
+                for k, bit in enumerate(npr):
+                    wt = wt * (w[t + 1 + k] if bit else 1 - w[t + 1 + k]) % R_MOD
+                for i in range(d2):
+                    ibits = [(i >> (l2 - 1 - k)) & 1 for k in range(l2)]
+                    npt = vs[:t] + [x] + list(npr)
+                    a = mle_eval(f0, npt + u0 + ibits)
+                    b = mle_eval(f1, npt + ibits + u1)
+                    acc = (acc + wt * a % R_MOD * b) % R_MOD
+            assert f[x] == acc
+    assert info["inner"].finals == [mle_eval(f0, vs[:ln] + u0 + vs[ln:]), mle_eval(f1, vs[:ln] + vs[ln:] + u1)]
+    assert len(buf) == 16 + 32 + 96 * ln + 16 + 32 * (1 + 3 * l2 + 2)
+    tv = Transcript(14)
+    claim0, finals, pts = P.matmul_ft_verify(buf, n, d1, d2, d3, tv)
+    assert claim0 == info["claim0"] and finals == info["inner"].finals and pts["v"] == vs
+    assert tv.digest() == ts.digest()
+
+
+def test_matmul_ft_verifier_rejects_tampering():
+    """Flip one bit in every field element of the proof: the verifier either rejects, or - for
+    the two kinds of value it hands to its caller to check against Y and the inputs, claim_0 and
+    the finals - returns a value that differs from the honest one."""
+    rng = np.random.default_rng(5)
+    n, d1, d2, d3 = 4, 2, 4, 2
+    x0 = rng.integers(-9, 10, (n, d1, d2))
+    x1 = rng.integers(-9, 10, (n, d2, d3))
+    buf, info = P.matmul_ft_prove(fr_array(x0), [n, d1, d2], fr_array(x1), [n, d2, d3], Transcript(2))
+    honest = (info["claim0"], info["inner"].finals)
+    inner_at = 16 + 32 + 96 * 2
+    slots = list(range(16, inner_at, 32)) + list(range(inner_at + 16, len(buf), 32))
+    assert len(slots) == 1 + 3 * 2 + 1 + 3 * 2 + 2
+    caught = 0
+    for off in slots:
+        bad = bytearray(buf)
+        bad[off] ^= 1
+        try:
+            claim0, finals, _ = P.matmul_ft_verify(bytes(bad), n, d1, d2, d3, Transcript(2))
+        except AssertionError:
+            caught += 1
+            continue
+        assert (claim0, finals) != honest
+    assert caught >= len(slots) - 3      # all but claim_0 and the two finals are rejected outright
