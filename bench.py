@@ -186,7 +186,9 @@ def main():
         z1 = torch.from_numpy(lay["Z"]).cuda().reshape(-1)
         mm_med, _ = timed(lambda: zk.sumcheck_matmul(ctx, x1, w1, zk.Transcript(CONFIG_SEED + 1)), 5)
         zr_med, _ = timed(lambda: zk.zkrelu_prove(ctx, z1, None, zk.Transcript(CONFIG_SEED + 1)), 5)
+        ft_med, _ = timed(lambda: zk.sumcheck_matmul_ft(ctx, x1, w1, zk.Transcript(CONFIG_SEED + 1)), 5)
         out["config"]["config1_matmul_us"] = 1e6 * mm_med
+        out["config"]["config1_matmul_ft_us"] = 1e6 * ft_med
         out["config"]["config1_zkrelu_us"] = 1e6 * zr_med
         del x1, w1, z1
         wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)

@@ -154,6 +154,24 @@ int sumcheck_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1,
                     int transpose_x1, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
                     zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints);
 
+/* sumcheck_matmul_ft: the same statement with the prover's messages of the optimized
+ * aggregated protocol (App. B, Protocol tensor-op-aggr-optimized).  For the log N stack
+ * rounds the prover sends f_t(0), f_t(1), f_t(2), the round polynomial without its
+ * factor beta~(w_t, .), which the verifier multiplies back:
+ *   f_t(x) = sum_{n'} beta~(w_[t+1:], n') sum_i X0~(v_<t, x, n', u0, i) X1~(v_<t, x, n', i, u1),
+ *   (1 - w_t) f_t(0) + w_t f_t(1) = claim,  next claim f_t(v_t);
+ * beta~(w, .) is never folded and the messages have degree 2.  Then the sumcheck of the
+ * single product sum_i X0~(v_n, u0, i) X1~(v_n, i, u1) follows (Eq.
+ * tensor-op-compressed-optimized): K = 2, degree 2.  Arguments and claims as for
+ * sumcheck_matmul.  Transcript: header "sumcheck_matmul_ft" (N, D1, D2, D3), one draw
+ * (w, u0, u1), "c" claim_0, per stack round "f" (three evaluations) and a draw, then the
+ * product sumcheck's rounds and finals (its claim_0 is not absorbed again).
+ * Proof: "ZKSF", log2 N, log2 D2, 0, claim_0, log2 N x 3 evaluations, then one SC block
+ * (K = 2, claim_0 = f_{n-1}(v_{n-1}), finals X0~(v_n,u0,v_i), X1~(v_n,v_i,u1)). */
+int sumcheck_matmul_ft(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1, int transpose_x0,
+                       int transpose_x1, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+                       zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints);
+
 /* sumcheck_hadamard: Eq. exm-hadamard-batched over the whole stack,
  *   Y~(p) = sum_b beta~(p,b) X0(b) X1(b),  p drawn over all log2(numel) variables.
  * claims (host, 3, may be NULL): Y~(p), X0~(v), X1~(v). */

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "zkdl_transcript_challenge", "zkdl_transcript_digest",
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
-    "mle_partial_eval", "sumcheck_product", "sumcheck_matmul", "sumcheck_hadamard",
+    "mle_partial_eval", "sumcheck_product", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_hadamard",
     "zkrelu_prove", "aggregate_prove", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read",
 ]
@@ -69,6 +69,7 @@ def load_library():
         "mle_partial_eval": [vp, vp, i, i, vp, sz, pp],
         "sumcheck_product": [vp, pp, i, vp, vp, psz, vp, vp, psz],
         "sumcheck_matmul": [vp, vp, vp, i, i, vp, vp, psz, vp, vp, psz],
+        "sumcheck_matmul_ft": [vp, vp, vp, i, i, vp, vp, psz, vp, vp, psz],
         "sumcheck_hadamard": [vp, vp, vp, vp, vp, psz, vp, vp, psz],
         "zkrelu_prove": [vp, vp, vp, u64, i, i, i, vp, vp, psz, vp, vp, psz],
         "aggregate_prove": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
@@ -301,6 +302,14 @@ def sumcheck_matmul(ctx, x0, x1, tr, transpose_x0=False, transpose_x1=False):
     _check(load_library().sumcheck_matmul(ctx.handle, x0.handle, x1.handle, int(transpose_x0),
                                           int(transpose_x1), tr.handle, o.proof, C.byref(o.proof_len),
                                           o.claims, o.points, C.byref(o.npoints)), "sumcheck_matmul", ctx)
+    return o.result()
+
+
+def sumcheck_matmul_ft(ctx, x0, x1, tr, transpose_x0=False, transpose_x1=False):
+    o = _Outputs(3)
+    _check(load_library().sumcheck_matmul_ft(ctx.handle, x0.handle, x1.handle, int(transpose_x0),
+                                             int(transpose_x1), tr.handle, o.proof, C.byref(o.proof_len),
+                                             o.claims, o.points, C.byref(o.npoints)), "sumcheck_matmul_ft", ctx)
     return o.result()
 
 

@@ -727,6 +727,91 @@ extern "C" int sumcheck_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_
     return rc != ZKDL_OK ? rc : rc2;
 }
 
+// Enqueues the optimized aggregated protocol for Y[n] = op(X0[n]) op(X1[n]) (App. B).  Final
+// claims are left in scal[scal_base .. +2): X0~, X1~.
+static int enqueue_matmul_ft(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1, int tr0, int tr1,
+                             int scal_base) {
+    if (X0->ndim != 3 || X1->ndim != 3 || X0->shape[0] != X1->shape[0]) return ZKDL_EINVAL;
+    const uint64_t N = X0->shape[0];
+    const uint64_t D1 = tr0 ? X0->shape[2] : X0->shape[1];
+    const uint64_t D2 = tr0 ? X0->shape[1] : X0->shape[2];
+    const uint64_t D2b = tr1 ? X1->shape[2] : X1->shape[1];
+    const uint64_t D3 = tr1 ? X1->shape[1] : X1->shape[2];
+    if (D2 != D2b) return ZKDL_EINVAL;
+    const int ln = ilog2_u64(N), l1 = ilog2_u64(D1), l2 = ilog2_u64(D2), l3 = ilog2_u64(D3);
+    if (ln > 13 || ctx->n_chal + ln + l1 + l3 + ln + l2 > ZK_MAX_CHAL) return ZKDL_EINVAL;
+    uint32_t hdr[4] = {(uint32_t)N, (uint32_t)D1, (uint32_t)D2, (uint32_t)D3};
+    zk_absorb_words(ctx, "sumcheck_matmul_ft", hdr, 4);
+    const int cw = ctx->n_chal, cu0 = cw + ln, cu1 = cu0 + l1;
+    zk_launch_draw(ctx, cw, ln + l1 + l3);
+    ctx->n_chal += ln + l1 + l3;
+    const Fr* chal = ctx->dev->chal;
+
+    const uint64_t len = N * D2;
+    // scratch: suffix tables of w (sizes N/2, N/4, .., 1), beta tables (D1, D3), two source tables,
+    // the work tables
+    void* mem = zk_alloc(ctx, (N + D1 + D3 + 2 * len) * 32 + zk_sumcheck_work_bytes(2, ln + l2));
+    if (!mem) return ZKDL_ENOMEM;
+    uint32_t* base = (uint32_t*)mem;
+    FrTab wsuf[16];
+    BetaJob jobs[16];
+    int nj = 0;
+    for (int t = 0; t < ln; ++t) {
+        const uint64_t rows = (uint64_t)1 << (ln - t - 1);
+        wsuf[t] = make_tab(base, rows);
+        base += 8 * rows;
+        jobs[nj++] = BetaJob{chal + cw + t + 1, ln - t - 1, wsuf[t]};
+    }
+    base = (uint32_t*)mem + 8 * N;
+    FrTab bu0 = make_tab(base, D1);
+    base += 8 * D1;
+    FrTab bu1 = make_tab(base, D3);
+    base += 8 * D3;
+    jobs[nj++] = BetaJob{chal + cu0, l1, bu0};
+    jobs[nj++] = BetaJob{chal + cu1, l3, bu1};
+    FrTab src[2];
+    for (int k = 0; k < 2; ++k) {
+        src[k] = make_tab(base, len);
+        base += 8 * len;
+    }
+    void* work = base;
+    int rc = zk_build_beta_many(ctx, jobs, nj);
+    if (rc == ZKDL_OK) {
+        FrTab s0 = make_tab(X0->data, X0->numel);
+        const void* sp = X0->kind == TK_FR ? (const void*)&s0 : X0->data;
+        if (!tr0) rc = zk_partial_eval(ctx, X0->kind, sp, N, D1, D2, bu0, src[0]);
+        else rc = zk_partial_eval(ctx, X0->kind, sp, N * D2, D1, 1, bu0, src[0]);
+    }
+    if (rc == ZKDL_OK) {
+        FrTab s1 = make_tab(X1->data, X1->numel);
+        const void* sp = X1->kind == TK_FR ? (const void*)&s1 : X1->data;
+        if (!tr1) rc = zk_partial_eval(ctx, X1->kind, sp, N * D2, D3, 1, bu1, src[1]);
+        else rc = zk_partial_eval(ctx, X1->kind, sp, N, D3, D2, bu1, src[1]);
+    }
+    if (rc == ZKDL_OK) rc = zk_matmul_ft(ctx, src, work, ln, l2, wsuf, cw, scal_base);
+    zk_free(ctx, mem);
+    return rc;
+}
+
+extern "C" int sumcheck_matmul_ft(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1,
+                                  int transpose_x0, int transpose_x1, zkdl_transcript* tr, uint8_t* proof,
+                                  size_t* proof_len, zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !X0 || !X1 || !tr) return ZKDL_EINVAL;
+    if (X0->ndim != 3 || X1->ndim != 3) return ZKDL_EINVAL;
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    rc = enqueue_matmul_ft(ctx, X0, X1, transpose_x0 != 0, transpose_x1 != 0, 0);
+    zkdl_fr tmp[2];
+    int ids[2] = {0, 1};
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 2, tmp);
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims && proof) {
+        memcpy(claims[0].le, proof + 16, 32);   // claim_0 = Y~(w, u0, u1)
+        claims[1] = tmp[0];
+        claims[2] = tmp[1];
+    }
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
 extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1,
                                  zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
                                  zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {

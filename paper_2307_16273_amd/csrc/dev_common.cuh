@@ -450,18 +450,20 @@ __device__ inline void wave_resolve_claim(DevState* st) {
 // Needs blockDim.x >= 192: while wave 0 hashes, wave 1 prepares the coefficients and wave 2
 // later writes the canonical form of the challenge.
 __device__ inline Fr block_round_challenge(TsShared& S, DevState* st, const Fr* g, int npts,
-                                           uint32_t proof_off, int chal_idx) {
+                                           uint32_t proof_off, int chal_idx, char label = 'g',
+                                           bool skip1 = true) {
     const int tid = threadIdx.x;
     uint32_t* proof_dst = (uint32_t*)(st->proof + proof_off);
     __syncthreads();
     // canonical forms (wave 0) | Lagrange coefficients (wave 1).  The transcript takes
     // g(0), g(2), .., g(npts-1): g(1) is fixed by the claim the transcript already determines.
+    // (skip1 = false, the f_t of the optimized matrix-product protocol: all evaluations.)
     if (tid < npts) {
         Fr plain = fr_from_mont_ni(g[tid]);
-        const int slot = tid == 0 ? 0 : tid - 1;
+        const int slot = (!skip1 || tid == 0) ? tid : tid - 1;
 #pragma unroll
         for (int l = 0; l < 8; ++l) {
-            if (tid != 1) S.canon[slot][l] = plain.v[l];
+            if (!skip1 || tid != 1) S.canon[slot][l] = plain.v[l];
             proof_dst[8 * tid + l] = plain.v[l];
         }
     } else if (tid >= 64 && tid < 64 + npts) {
@@ -477,7 +479,7 @@ __device__ inline Fr block_round_challenge(TsShared& S, DevState* st, const Fr* 
         }
         S.tmp[k] = c;
     }
-    const int prep = block_absorb1(S, 'g', npts - 1, true);
+    const int prep = block_absorb1(S, label, skip1 ? npts - 1 : npts, true);
     Fr v;
     if (prep >= 0) {
         // challenge hashes on the schedules prepared during the absorb: lanes 0, 1 (the two

@@ -121,8 +121,10 @@ struct FinArgs {
     DevState* st;
     int chal_idx;
     uint32_t proof_off;    // where g_t(0..npts-1) go
-    int first;             // round 0: claim_0 = g(0) + g(1) is written and absorbed first
+    int first;             // 1: claim_0 = g(0) + g(1) is written and absorbed first; 2: written only
+                           // (the transcript already fixes it)
     uint32_t claim_off;
+    uint32_t claim_copy_off;   // != 0: a second place in the proof for claim_0
     int derive1;           // g(1) = running claim - g(0) (the round kernel left it out)
 };
 
@@ -144,10 +146,16 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_finalise(FinArgs a) {
     block_reduce_partials(a.part, a.nblk, a.npts, g, a.derive1 != 0);
     if (a.derive1 && threadIdx.x == 0) g[1] = fr_sub(claim_s, g[0]);
     __syncthreads();
-    if (a.first) {
+    if (a.first == 1) {
         if (threadIdx.x == 0) g[ZK_MAX_EVALS] = fr_add(g[0], g[1]);
         __syncthreads();
         block_absorb_frs(S, 'c', &g[ZK_MAX_EVALS], 1, (uint32_t*)(st->proof + a.claim_off));
+    }
+    if (a.first && (a.first == 2 || a.claim_copy_off) && threadIdx.x == 64) {
+        const Fr plain = fr_from_mont_ni(fr_add(g[0], g[1]));
+        uint32_t* dst = (uint32_t*)(st->proof + (a.first == 2 ? a.claim_off : a.claim_copy_off));
+#pragma unroll
+        for (int l = 0; l < 8; ++l) dst[l] = plain.v[l];
     }
     block_round_challenge(S, st, g, a.npts, a.proof_off, a.chal_idx);
     // the next claim g_t(v_t) is owed: whoever needs it evaluates it from these coefficients
@@ -161,6 +169,22 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_sc_finalise(FinArgs a) {
     block_ts_store(S, st);
 }
 
+static FinArgs zk_fin_args(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_t proof_off, int first,
+                           uint32_t claim_off, int derive1) {
+    FinArgs fa;
+    fa.part = ctx->partials;
+    fa.nblk = nblk;
+    fa.npts = npts;
+    fa.st = ctx->dev;
+    fa.chal_idx = chal_idx;
+    fa.proof_off = proof_off;
+    fa.first = first;
+    fa.claim_off = claim_off;
+    fa.claim_copy_off = 0;
+    fa.derive1 = derive1;
+    return fa;
+}
+
 void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_t proof_off, int first,
                         uint32_t claim_off, int derive1) {
     FinArgs fa;
@@ -172,6 +196,7 @@ void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_
     fa.proof_off = proof_off;
     fa.first = first;
     fa.claim_off = claim_off;
+    fa.claim_copy_off = 0;
     fa.derive1 = derive1;
     zk_prof_begin(ctx, ZKDL_PROF_FINALISE, 32.0 * npts);
     hipLaunchKernelGGL(k_sc_finalise, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, fa);
@@ -190,6 +215,8 @@ struct FinishArgs {
     uint32_t finals_off;
     int absorb_claim;    // d == 0: claim_0 = product of the single entries
     uint32_t claim_off;
+    uint32_t claim_copy_off;         // != 0 (with absorb_claim): a second place in the proof for claim_0
+    uint32_t write_owed_claim_off;   // != 0: the running claim (possibly still owed) is written there
 };
 
 __global__ __launch_bounds__(64) void k_sc_finish(FinishArgs a) {
@@ -197,6 +224,15 @@ __global__ __launch_bounds__(64) void k_sc_finish(FinishArgs a) {
     __shared__ Fr f[4];
     DevState* st = a.st;
     block_ts_load(S, st);
+    if (a.write_owed_claim_off) {      // one wave: blockDim.x = 64
+        wave_resolve_claim(st);
+        if (threadIdx.x == 0) {
+            const Fr plain = fr_from_mont_ni(st->claim);
+            uint32_t* dst = (uint32_t*)(st->proof + a.write_owed_claim_off);
+#pragma unroll
+            for (int l = 0; l < 8; ++l) dst[l] = plain.v[l];
+        }
+    }
     if (threadIdx.x < (unsigned)a.K) {
         const int k = threadIdx.x;
         Fr lo, hi = fr_zero();
@@ -222,6 +258,8 @@ __global__ __launch_bounds__(64) void k_sc_finish(FinishArgs a) {
         }
         __syncthreads();
         block_absorb_frs(S, 'c', &f[3], 1, (uint32_t*)(st->proof + a.claim_off));
+        if (a.claim_copy_off && threadIdx.x < 8)
+            ((uint32_t*)(st->proof + a.claim_copy_off))[threadIdx.x] = S.canon[0][threadIdx.x];
     }
     block_absorb_frs(S, 'f', f, a.K, (uint32_t*)(st->proof + a.finals_off));
     block_ts_store(S, st);
@@ -481,9 +519,261 @@ int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, void* work_mem, 
     fi.finals_off = finals_off;
     fi.absorb_claim = (d == 0);
     fi.claim_off = claim_off;
+    fi.claim_copy_off = 0;
+    fi.write_owed_claim_off = 0;
     hipLaunchKernelGGL(k_sc_finish, dim3(1), dim3(64), 0, ctx->stream, fi);
     return ZKDL_OK;
 }
+
+// ---------------------------------------------------------------------------
+// Optimized aggregated protocol for the batched matrix product (App. B, Protocol
+// tensor-op-aggr-optimized): stack rounds send f_t, the round polynomial without its factor
+// beta~(w_t, .); beta~(w, .) is never a table that gets folded.
+//   f_t(x) = sum_{n'} beta~(w_[t+1:], n') sum_i X0'(x, n', i) X1'(x, n', i),  x = 0, 1, 2,
+// X0', X1' the two tables with the earlier stack variables bound.  Pair index b = (n', i),
+// partner b + m.  MODE as in k_sc_round: 0 first round (packed sources), 1 fold the previous
+// challenge while reading the packed sources, 2 the same in place on the work tables.
+// The weight multiplies the first factor's line once (w lo, w hi, and 2 w hi - w lo at x = 2),
+// so a pair costs five products and, after the first round, four folds.
+// ---------------------------------------------------------------------------
+struct FtRoundArgs {
+    FrTab src8[2];
+    F9Tab work[2];
+    uint64_t m;        // pair indices this round: (rows / 2) * inner
+    int log_inner;     // row n' of pair index b is b >> log_inner
+    FrTab wsuf;        // beta~(w_[t+1:], n'), rows / 2 entries
+    const Fr* chal;    // challenge of the previous round (MODE != 0)
+    Fr* part;          // block b: f(0), f(1), f(2) at part[3 b + x]
+};
+
+template <int MODE>
+__global__ __launch_bounds__(ZK_BLOCK) void k_ft_round(FtRoundArgs a) {
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    F9 acc[3];
+#pragma unroll
+    for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
+    F9 v = f9_zero();
+    if (MODE != 0) v = fr_unpack(*a.chal);
+    const uint64_t m = a.m;
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m;
+         b += (uint64_t)gridDim.x * blockDim.x) {
+        F9 lo[2], hi[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (MODE == 0) {
+                lo[k] = fr_unpack(tab_ld(a.src8[k], b));
+                hi[k] = fr_unpack(tab_ld(a.src8[k], b + m));
+            } else {
+                F9 t0, t1, t2, t3;
+                if (MODE == 1) {
+                    t0 = fr_unpack(tab_ld(a.src8[k], b));
+                    t1 = fr_unpack(tab_ld(a.src8[k], b + m));
+                    t2 = fr_unpack(tab_ld(a.src8[k], b + 2 * m));
+                    t3 = fr_unpack(tab_ld(a.src8[k], b + 3 * m));
+                } else {
+                    t0 = f9tab_ld(a.work[k], b);
+                    t1 = f9tab_ld(a.work[k], b + m);
+                    t2 = f9tab_ld(a.work[k], b + 2 * m);
+                    t3 = f9tab_ld(a.work[k], b + 3 * m);
+                }
+                lo[k] = f9_norm_reduce(f9_add(t0, f9_mul(f9_sub(t2, t0), v)));
+                hi[k] = f9_norm_reduce(f9_add(t1, f9_mul(f9_sub(t3, t1), v)));
+                f9tab_st(a.work[k], b, lo[k]);
+                f9tab_st(a.work[k], b + m, hi[k]);
+            }
+        }
+        const F9 w = fr_unpack(tab_ld(a.wsuf, b >> a.log_inner));
+        // first factor times the weight: normal values below 2 r
+        const F9 wl = f9_mul(lo[0], w), wh = f9_mul(hi[0], w);
+        const F9 w2 = f9_norm(f9_add(wh, f9_norm(f9_sub(wh, wl))));          // at x = 2
+        const F9 e2 = f9_add(hi[1], f9_norm(f9_sub(hi[1], lo[1])));           // second factor at x = 2
+        acc[0] = f9_add(acc[0], f9_mul(wl, lo[1]));
+        acc[1] = f9_add(acc[1], f9_mul(wh, hi[1]));
+        acc[2] = f9_add(acc[2], f9_mul(w2, e2));
+#pragma unroll
+        for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
+    }
+    const Fr s = block_sum_lazy<3>(acc, red);
+    if (threadIdx.x < 3) a.part[(uint64_t)blockIdx.x * 3 + threadIdx.x] = s;
+}
+
+struct FtFinArgs {
+    const Fr* part;
+    int nblk;
+    DevState* st;
+    int chal_idx;
+    uint32_t proof_off;    // where f_t(0..2) go
+    int first;             // round 0: claim_0 = (1 - w_0) f_0(0) + w_0 f_0(1) is written and absorbed first
+    uint32_t claim_off;
+    int w_idx;             // challenge index of w_0
+};
+
+// Closes a stack round: sums the partials, [claim_0], f_t into the proof and the transcript,
+// the round's challenge; the next claim f_t(v_t) is left owed.
+__global__ __launch_bounds__(ZK_BLOCK) void k_ft_finalise(FtFinArgs a) {
+    __shared__ TsShared S;
+    __shared__ Fr g[ZK_MAX_EVALS + 1];
+    DevState* st = a.st;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    block_ts_load(S, st);
+    block_reduce_partials(a.part, a.nblk, 3, g);
+    if (a.first) {
+        if (threadIdx.x == 0) {
+            g[ZK_MAX_EVALS] = fr_add(g[0], fr_mul_ni(st->chal[a.w_idx], fr_sub(g[1], g[0])));
+            st->lag_npts = 0;
+        }
+        __syncthreads();
+        block_absorb_frs(S, 'c', &g[ZK_MAX_EVALS], 1, (uint32_t*)(st->proof + a.claim_off));
+    }
+    block_round_challenge(S, st, g, 3, a.proof_off, a.chal_idx, 'f', false);
+    if (wave == 1) {
+        if (lane < 3) st->lag[lane] = S.tmp[lane];
+        if (lane == 0) {
+            st->lag_npts = 3;
+            st->lag_chal = (uint32_t)a.chal_idx;
+        }
+    }
+    block_ts_store(S, st);
+}
+
+// Stack rounds with f_t, then the single-product sumcheck (K = 2) on the bound tables.
+// src: X0'[n, i], X1'[n, i] (packed, 2^(ln + l2) entries each); wsuf[t]: beta~(w_[t+1:], .);
+// w_idx: challenge index of w_0.  Proof: "ZKSF" block, then the SC block of the second part.
+int zk_matmul_ft(zkdl_ctx* ctx, const FrTab* src, void* work_mem, int ln, int l2, const FrTab* wsuf, int w_idx,
+                 int finals_scal_base) {
+    const int d = ln + l2;
+    if (ctx->n_chal + d > ZK_MAX_CHAL) return ZKDL_EINVAL;
+    zk_flush_frames(ctx);
+    uint32_t hdr[4] = {0x46534B5Au, (uint32_t)ln, (uint32_t)l2, 0};
+    zk_write_proof_words(ctx, hdr, 4);
+    const uint32_t outer_claim_off = (uint32_t)ctx->proof_len;
+    const uint32_t stack_off = outer_claim_off + 32;
+    ctx->proof_len = stack_off + 96 * (size_t)ln;
+    uint32_t ihdr[4] = {SC_MAGIC, 2, 2, (uint32_t)l2};
+    zk_write_proof_words(ctx, ihdr, 4);
+    const uint32_t inner_claim_off = (uint32_t)ctx->proof_len;
+    const uint32_t inner_rounds_off = inner_claim_off + 32;
+    const uint32_t finals_off = inner_rounds_off + 96 * (uint32_t)l2;
+    if (finals_off + 64 > (uint32_t)ZK_PROOF_CAP) return ZKDL_ESMALL;
+    ctx->proof_len = finals_off + 64;
+
+    const uint64_t half = d >= 1 ? ((uint64_t)1 << (d - 1)) : 1;
+    F9Tab work[2];
+    for (int k = 0; k < 2; ++k) {
+        work[k].p = (uint32_t*)work_mem + (size_t)k * half * 9;
+        work[k].ps = half;
+    }
+    const int first_chal = ctx->n_chal;
+    constexpr int SC_TAIL_LOG = 10;
+    // the tail kernel takes single-product rounds only, and never the first of them
+    int t_tail = d >= 3 ? (d - SC_TAIL_LOG > 2 ? d - SC_TAIL_LOG : 2) : d;
+    if (t_tail < ln + 1) t_tail = ln + 1;
+    if (t_tail > d) t_tail = d;
+    for (int t = 0; t < t_tail; ++t) {
+        const int mode = t == 0 ? 0 : t == 1 ? 1 : 2;
+        const uint64_t m = (uint64_t)1 << (d - t - 1);
+        const uint64_t want = (m + ZK_BLOCK - 1) / ZK_BLOCK;
+        const unsigned grid = (unsigned)(want > ZK_MAX_PART_BLOCKS ? ZK_MAX_PART_BLOCKS : want);
+        const Fr* prev = mode ? &ctx->dev->chal[first_chal + t - 1] : nullptr;
+        if (t < ln) {
+            FtRoundArgs fa;
+            for (int k = 0; k < 2; ++k) {
+                fa.src8[k] = src[k];
+                fa.work[k] = work[k];
+            }
+            fa.m = m;
+            fa.log_inner = l2;
+            fa.wsuf = wsuf[t];
+            fa.chal = prev;
+            fa.part = ctx->partials;
+            zk_prof_begin(ctx, mode ? ZKDL_PROF_SC_ROUND_FUSED : ZKDL_PROF_SC_ROUND_FIRST,
+                          2.0 * (mode ? 192.0 : 64.0) * (double)m);
+            if (mode == 0) hipLaunchKernelGGL(k_ft_round<0>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+            else if (mode == 1) hipLaunchKernelGGL(k_ft_round<1>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+            else hipLaunchKernelGGL(k_ft_round<2>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+            zk_prof_end(ctx);
+            FtFinArgs ff;
+            ff.part = ctx->partials;
+            ff.nblk = (int)grid;
+            ff.st = ctx->dev;
+            ff.chal_idx = ctx->n_chal++;
+            ff.proof_off = stack_off + 96 * (uint32_t)t;
+            ff.first = t == 0;
+            ff.claim_off = outer_claim_off;
+            ff.w_idx = w_idx;
+            zk_prof_begin(ctx, ZKDL_PROF_FINALISE, 96.0);
+            hipLaunchKernelGGL(k_ft_finalise, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ff);
+            zk_prof_end(ctx);
+            continue;
+        }
+        RoundArgs ra;
+        for (int k = 0; k < 2; ++k) {
+            ra.src8[k] = src[k];
+            ra.work[k] = work[k];
+        }
+        ra.src8[2] = src[0];
+        ra.work[2] = work[0];
+        ra.m = m;
+        ra.chal = prev;
+        ra.part = ctx->partials;
+        zk_prof_begin(ctx, mode ? ZKDL_PROF_SC_ROUND_FUSED : ZKDL_PROF_SC_ROUND_FIRST,
+                      2.0 * (mode ? 192.0 : 64.0) * (double)m);
+        launch_round<2>(ctx, mode, ra, grid);
+        zk_prof_end(ctx);
+        // first single-product round: its claim_0 is f_{n-1}(v_{n-1}), which the transcript already
+        // fixes (written, not absorbed); without stack rounds it is Y~(u0, u1) itself (absorbed, and
+        // copied into the outer block)
+        FinArgs fin = zk_fin_args(ctx, (int)grid, 3, ctx->n_chal++, inner_rounds_off + 96 * (uint32_t)(t - ln),
+                                  t == ln ? (ln == 0 ? 1 : 2) : 0, inner_claim_off, mode != 0);
+        fin.claim_copy_off = (t == ln && ln == 0) ? outer_claim_off : 0;
+        zk_prof_begin(ctx, ZKDL_PROF_FINALISE, 96.0);
+        hipLaunchKernelGGL(k_sc_finalise, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, fin);
+        zk_prof_end(ctx);
+    }
+    if (t_tail < d) {
+        ScTailArgs ta;
+        for (int k = 0; k < 2; ++k) {
+            ta.ra.src8[k] = src[k];
+            ta.ra.work[k] = work[k];
+        }
+        ta.ra.src8[2] = src[0];
+        ta.ra.work[2] = work[0];
+        ta.ra.m = (uint64_t)1 << (d - t_tail - 1);
+        ta.ra.chal = nullptr;
+        ta.ra.part = nullptr;
+        ta.rounds = d - t_tail;
+        ta.first_chal = first_chal + t_tail - 1;
+        ta.st = ctx->dev;
+        ta.rounds_off = inner_rounds_off + 96 * (uint32_t)(t_tail - ln);
+        ta.finals_off = finals_off;
+        ta.scal_base = finals_scal_base;
+        ctx->n_chal += d - t_tail;
+        launch_tail<2>(ctx, ta);
+        return ZKDL_OK;
+    }
+    FinishArgs fi;
+    for (int k = 0; k < 2; ++k) {
+        fi.src[k] = src[k];
+        fi.work[k] = work[k];
+    }
+    fi.src[2] = src[0];
+    fi.work[2] = work[0];
+    fi.from_work = d >= 2;
+    fi.K = 2;
+    fi.fold = d >= 1;
+    fi.chal = d >= 1 ? &ctx->dev->chal[first_chal + d - 1] : nullptr;
+    fi.st = ctx->dev;
+    fi.scal_base = finals_scal_base;
+    fi.finals_off = finals_off;
+    fi.absorb_claim = (d == 0);
+    fi.claim_off = inner_claim_off;
+    fi.claim_copy_off = d == 0 ? outer_claim_off : 0;
+    fi.write_owed_claim_off = (l2 == 0 && ln >= 1) ? inner_claim_off : 0;
+    hipLaunchKernelGGL(k_sc_finish, dim3(1), dim3(64), 0, ctx->stream, fi);
+    return ZKDL_OK;
+}
+
+
 
 // ---- transcript-only kernels -----------------------------------------------------
 struct FramesArg {

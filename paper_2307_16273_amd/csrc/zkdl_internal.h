@@ -147,6 +147,9 @@ void zk_launch_draw(zkdl_ctx* ctx, int chal_base, int count);
 static inline void zk_flush_frames(zkdl_ctx* ctx) { zk_launch_draw(ctx, 0, 0); }
 
 // ---- k_zkrelu.hip ----------------------------------------------------------------
+// optimized aggregated matrix-product protocol: stack rounds with f_t, then the single-product sumcheck
+int zk_matmul_ft(zkdl_ctx* ctx, const FrTab* src, void* work_mem, int ln, int l2, const FrTab* wsuf, int w_idx,
+                 int finals_scal_base);
 int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q, int R);
 
 // ---- api.hip -----------------------------------------------------------------------

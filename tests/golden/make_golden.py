@@ -46,6 +46,18 @@ def matmul_case():
             "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
 
 
+def matmul_ft_case():
+    """The same product with the messages of the optimized aggregated protocol (App. B)."""
+    rng = np.random.default_rng(20230717)
+    x0 = rng.integers(-50, 50, (2, 2, 4)).astype(np.int64)
+    x1 = rng.integers(-50, 50, (2, 4, 2)).astype(np.int64)
+    ts = Transcript(8)
+    buf, info = P.matmul_ft_prove(fr_array(x0), [2, 2, 4], fr_array(x1), [2, 4, 2], ts)
+    return {"protocol": "sumcheck_matmul_ft", "cite": "App. B, Protocol tensor-op-aggr-optimized", "seed": 8,
+            "x0": x0.reshape(-1).tolist(), "x0_shape": [2, 2, 4], "x1": x1.reshape(-1).tolist(), "x1_shape": [2, 4, 2],
+            "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
+
+
 def zkrelu_case():
     """zkReLU (Sec. 3.1, App. A): D = 4, Q = 5, R = 3, with gradients."""
     z = [77, -128, -1, 100]
@@ -70,6 +82,7 @@ def aggregate_case():
 
 if __name__ == "__main__":
     for name, fn in (("product_k3_d3", product_case), ("matmul_n2_2x4x2", matmul_case),
+                     ("matmul_ft_n2_2x4x2", matmul_ft_case),
                      ("zkrelu_d4_q5_r3", zkrelu_case), ("aggregate_l2_w4_b2_t2", aggregate_case)):
         with open(os.path.join(HERE, name + ".json"), "w") as f:
             json.dump(fn(), f, indent=1)

@@ -26,6 +26,8 @@ def oracle_run(g):
         buf = P.product_prove([fr_array_from_le(bytes.fromhex(h), 8) for h in g["tables_le_hex"]], ts)[0]
     elif g["protocol"] == "sumcheck_matmul":
         buf = P.matmul_prove(fr_array(np.array(g["x0"])), g["x0_shape"], fr_array(np.array(g["x1"])), g["x1_shape"], ts)[0]
+    elif g["protocol"] == "sumcheck_matmul_ft":
+        buf = P.matmul_ft_prove(fr_array(np.array(g["x0"])), g["x0_shape"], fr_array(np.array(g["x1"])), g["x1_shape"], ts)[0]
     elif g["protocol"] == "zkrelu_prove":
         buf = P.zkrelu_prove(g["Z"], g["GA"], g["Q"], g["R"], ts)[0]
     else:
@@ -34,7 +36,7 @@ def oracle_run(g):
     return bytes(buf), ts
 
 
-NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "zkrelu_d4_q5_r3", "aggregate_l2_w4_b2_t2"]
+NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "zkrelu_d4_q5_r3", "aggregate_l2_w4_b2_t2"]
 
 
 @pytest.mark.parametrize("name", NAMES)
@@ -56,10 +58,10 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
     if g["protocol"] == "sumcheck_product":
         tabs = [lib.fr_tensor_upload(ctx, bytes.fromhex(h), (8,)) for h in g["tables_le_hex"]]
         got = lib.sumcheck_product(ctx, tabs, tr)
-    elif g["protocol"] == "sumcheck_matmul":
+    elif g["protocol"] in ("sumcheck_matmul", "sumcheck_matmul_ft"):
         x0 = lib.fr_tensor_upload(ctx, np.array(g["x0"], dtype=np.int64), tuple(g["x0_shape"]))
         x1 = lib.fr_tensor_upload(ctx, np.array(g["x1"], dtype=np.int64), tuple(g["x1_shape"]))
-        got = lib.sumcheck_matmul(ctx, x0, x1, tr)
+        got = getattr(lib, g["protocol"])(ctx, x0, x1, tr)
     elif g["protocol"] == "zkrelu_prove":
         got = lib.zkrelu_prove(ctx, np.array(g["Z"], dtype=np.int64), np.array(g["GA"], dtype=np.int64), tr, g["Q"], g["R"])
     else:

@@ -144,6 +144,46 @@ def test_sumcheck_matmul(lib, ctx, n, d1, d2, d3, t0, t1, kind):
     assert tr.digest() == ots.digest()
 
 
+@pytest.mark.parametrize("n,d1,d2,d3,t0,t1,kind", [
+    (1, 16, 256, 256, False, False, "i32"),      # no stack rounds: the single-product sumcheck alone
+    (1, 2, 1, 2, False, False, "fr"),            # neither stack nor product rounds
+    (4, 2, 1, 2, False, False, "i32"),           # stack rounds only (D2 = 1)
+    (2, 4, 1, 2, False, False, "fr"),
+    (2, 1, 2, 1, False, False, "fr"),
+    (4, 8, 32, 16, False, False, "fr"),
+    (4, 8, 32, 16, True, False, "i32"),
+    (4, 8, 32, 16, False, True, "i32"),
+    (8, 4, 64, 64, True, True, "i32"),
+    (16, 2, 1024, 2, False, False, "i32"),       # 14 rounds: the single-block tail takes the last ten
+    (128, 2, 16, 2, False, False, "i32"),        # seven stack rounds
+])
+def test_sumcheck_matmul_ft(lib, ctx, n, d1, d2, d3, t0, t1, kind):
+    """The optimized aggregated protocol (stack rounds with f_t, then the single-product
+    sumcheck): proof bytes, challenges, claims and transcript against the oracle."""
+    import torch
+    say(f"sumcheck_matmul_ft N={n} D=({d1},{d2},{d3}) tr=({t0},{t1}) {kind}")
+    rng = np.random.default_rng(n * 1000 + d1 + d2 + d3 + 1)
+    x0 = rng.integers(-2 ** 31, 2 ** 31, (n, d1, d2), dtype=np.int64).astype(np.int32)
+    x1 = rng.integers(-2 ** 31, 2 ** 31, (n, d2, d3), dtype=np.int64).astype(np.int32)
+    s0 = np.ascontiguousarray(np.transpose(x0, (0, 2, 1))) if t0 else x0     # what is stored
+    s1 = np.ascontiguousarray(np.transpose(x1, (0, 2, 1))) if t1 else x1
+    if kind == "i32":
+        a = lib.tensor_wrap_int(ctx, torch.from_numpy(s0).cuda())
+        b = lib.tensor_wrap_int(ctx, torch.from_numpy(s1).cuda())
+    else:
+        a = lib.fr_tensor_upload(ctx, s0, s0.shape)
+        b = lib.fr_tensor_upload(ctx, s1, s1.shape)
+    tr = lib.Transcript(6)
+    got = lib.sumcheck_matmul_ft(ctx, a, b, tr, t0, t1)
+    ots = OracleTranscript(6)
+    buf, info = P.matmul_ft_prove(fr_array(x0), [n, d1, d2], fr_array(x1), [n, d2, d3], ots)
+    assert got["proof"] == buf
+    assert got["points"] == ots.challenges
+    assert got["claims"] == [info["claim0"]] + info["inner"].finals
+    assert tr.digest() == ots.digest()
+    P.matmul_ft_verify(got["proof"], n, d1, d2, d3, OracleTranscript(6))
+
+
 @pytest.mark.parametrize("shape", [(1,), (2, 4, 4), (4, 64, 16)])
 def test_sumcheck_hadamard(lib, ctx, shape):
     say(f"sumcheck_hadamard shape={shape}")
