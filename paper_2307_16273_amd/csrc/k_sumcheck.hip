@@ -1,6 +1,7 @@
 // Product sumcheck rounds (Sec. 2.2; round structure of the protocols in App. B):
 // fused fold-and-evaluate kernel, per-round finaliser with the device-side
-// transcript, final fold.
+// transcript, the last rounds in one block, final fold; the stack rounds of the
+// optimized aggregated matrix-product protocol (f_t without its beta factor).
 #include <string.h>
 #include "dev_common.cuh"
 

@@ -10,15 +10,24 @@
 //    sum_j aux(k,i,j) s(j) is the integer itself (Eqs. aux-Z, aux-GA) while
 //    sum_j aux(k,i,j) s'(j) is the rescaled integer.  Folding over i commutes with
 //    these sums, so during the i-rounds they run on D-sized tables
-//    (k_zk_lin): beta*Z, beta*(1-sign)*Z', beta*G_A, beta*(1-sign)*G_A'.
-//  * Only the binarity terms need the D x (Q+R) tables (k_zk_bin*).  Their
+//    (lin_body): beta*Z, beta*(1-sign)*Z', beta*G_A, beta*(1-sign)*G_A'.
+//  * Only the binarity terms need the D x (Q+R) tables (bin*_body).  Their
 //    equality factor splits as beta~(u_bin,(i,j)) = beta_I(i) beta_J(j).
-//    Rounds 0 and 1 work on the integers directly: aux is binary, so in round 0
-//    a(x)^2 - a(x) = (x^2 - x) [bit_lo != bit_hi], and after the first challenge an
-//    entry is one of {0, 1, v, 1-v}, which makes round 1 a table look-up (k_zk_bin1).
-//    After the second challenge the columns are written out once (k_zk_mat2, one of
-//    16 values per entry), column-major: entry (k, j, i) at plane (k*(Q+R)+j), so
-//    that threads over i read coalesced limb planes; D/4 rows.
+//    Rounds 0, 1 and 2 work on the integers directly: aux is binary, so in round 0
+//    a(x)^2 - a(x) = (x^2 - x) [bit_lo != bit_hi]; after the first challenge an
+//    entry is one of {0, 1, v, 1-v}, which makes round 1 a table look-up by bit masks
+//    (bin1_body); after the second it is one of 16 values and a pair one of 256
+//    combinations, so round 2 reads q(x) from a 256-entry table (bin2_body).
+//    After the third challenge the columns are written out once (k_zk_mat3, one of
+//    256 values per entry), column-major: entry (k, j, i) at plane (k*(Q+R)+j), so
+//    that threads over i read coalesced limb planes; D/8 rows.  Later rounds fold them
+//    (binl_body).  sum_j beta_J(j) q_j(x) is accumulated as 64-bit columns and reduced
+//    once per pair index; beta_I is folded by the binarity blocks themselves between
+//    two buffers, so they share no table with the linear blocks.
+//  * One launch per i-round (k_zk_round): the first blocks take the linear equations,
+//    the others the binarity terms; the round's finaliser adds up all partial sums.
+//    Rounds with few pairs spread a pair over more threads (lin_body_small, column
+//    and slice chunks) so that no thread carries a long chain of products.
 //  * The j-rounds (log2 J of them) and the merge run on 64/128-entry tables in a
 //    single block (k_zk_tail) together with their transcript steps.
 #include "dev_common.cuh"
