@@ -195,6 +195,88 @@ def matmul_ft_verify(buf, n, d1, d2, d3, ts):
 
 
 # --------------------------------------------------------------------------
+# re-indexing of stacked tensors (Sec. 4, Eq. sc-reindex; Protocol zkdl, the re-indexing line)
+# --------------------------------------------------------------------------
+RI_MAGIC = 0x49524B5A   # "ZKRI"
+
+
+def _reindex_statement_digest(n, d, maps, points, u):
+    """SHA-256 of the public part of the statement: shapes, index maps, points."""
+    import hashlib
+    h = hashlib.sha256()
+    h.update(struct.pack("<III", n, d, len(maps)))
+    for m in maps:
+        h.update(struct.pack("<I", len(m)))
+        h.update(b"".join(struct.pack("<i", int(j)) for j in m))
+    for pt in points:
+        h.update(b"".join(to_le(x) for x in pt))
+    h.update(b"".join(to_le(x) for x in u))
+    return h.digest()
+
+
+def reindex_weights(n, maps, points, r):
+    """P[i] = sum_k r_k sum_j beta~(u_k, j) p_k(i, j), p_k(i, j) = [maps[k][j] == i]."""
+    p = [0] * n
+    for k, m in enumerate(maps):
+        bk = beta_table(points[k])
+        for j, i in enumerate(m):
+            if i >= 0:
+                p[i] = (p[i] + r[k] * int(bk[j])) % R_MOD
+    return p
+
+
+def reindex_prove(x, n, d, maps, points, u, ts):
+    """K sub-stacks X_k = (X^(maps[k][0]), X^(maps[k][1]), ..) of the stack X [N, D] (an entry
+    -1 is a zero tensor: padding), each with a claim X_k~(u_k, u) at its own stack point u_k
+    and the common point u over the other dimensions.  With verifier coefficients r_k,
+      sum_k r_k X_k~(u_k, u) = sum_i P[i] X~(i, u),  P as in reindex_weights,
+    is proved by a sumcheck over i (two tables, degree 2), which leaves ONE claim X~(v, u) on
+    the whole stack; the verifier evaluates P~(v) itself (Eq. sc-reindex).
+
+    Transcript: "reindex" (digest of shapes, maps and points: they are public or come from the
+    preceding sumchecks); "c" the K claims; one draw of K coefficients; then the product
+    sumcheck on (P, X~(., u)) as in product_prove's rounds (its claim_0 = sum_k r_k c_k is
+    absorbed like any claim_0).  Proof: "ZKRI", N, D, K, 0, the K claims, one SC block.
+    """
+    k_sub = len(maps)
+    assert 1 <= k_sub <= 8 and len(points) == k_sub and len(u) == ilog2(d)
+    for m, pt in zip(maps, points):
+        assert len(pt) == ilog2(len(m)) and all(-1 <= int(j) < n for j in m)
+    ts.absorb(b"reindex", _reindex_statement_digest(n, d, maps, points, u))
+    t, _ = partial_eval(x, [n, d], 1, 2, u)                  # X~(i, u) for every i
+    t = [int(v) for v in t]
+    claims = []
+    for m, pt in zip(maps, points):
+        bk = beta_table(pt)
+        claims.append(sum(int(bk[j]) * t[i] for j, i in enumerate(m) if i >= 0) % R_MOD)
+    ts.absorb_fr(b"c", claims)
+    r = ts.challenges_vec(k_sub)
+    p = reindex_weights(n, maps, points, r)
+    proof, vs = prove([np.array(p, dtype=object), np.array(t, dtype=object)], [(1, [0, 1])], 2, ts)
+    assert proof.claim0 == sum(rk * ck for rk, ck in zip(r, claims)) % R_MOD
+    out = [struct.pack("<IIII", RI_MAGIC, n, d, k_sub)] + [to_le(c) for c in claims] + [proof.to_bytes()]
+    return b"".join(out), dict(claims=claims, r=r, v=vs, inner=proof, weights=p)
+
+
+def reindex_verify(buf, n, d, maps, points, u, ts):
+    """Returns (the K claims, the point v, the remaining claim X~(v, u))."""
+    magic, n_, d_, k_sub = struct.unpack_from("<IIII", buf, 0)
+    assert magic == RI_MAGIC and n_ == n and d_ == d and k_sub == len(maps)
+    ts.absorb(b"reindex", _reindex_statement_digest(n, d, maps, points, u))
+    claims = [from_le(buf[16 + 32 * k:48 + 32 * k]) for k in range(k_sub)]
+    ts.absorb_fr(b"c", claims)
+    r = ts.challenges_vec(k_sub)
+    proof, end = SumcheckProof.from_bytes(buf, 16 + 32 * k_sub)
+    assert end == len(buf) and proof.n_finals == 2 and proof.degree == 2 and len(proof.rounds) == ilog2(n)
+    expect0 = sum(rk * ck for rk, ck in zip(r, claims)) % R_MOD
+    last, vs = verify_rounds(proof, ts, expected_claim0=expect0)
+    pw, xw = proof.finals
+    assert pw * xw % R_MOD == last, "final claim mismatch"
+    assert pw == mle_eval(np.array(reindex_weights(n, maps, points, r), dtype=object), vs), "P~(v) mismatch"
+    return claims, vs, xw
+
+
+# --------------------------------------------------------------------------
 # batched Hadamard product (Eq. exm-hadamard-batched)
 # --------------------------------------------------------------------------
 def hadamard_prove(x0, x1, ts):

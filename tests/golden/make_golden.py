@@ -2,7 +2,7 @@
 
 Run from the repository root:  python tests/golden/make_golden.py
 Calls only `oracle/` and the seeded input generators in `workloads/`.  The files freeze
-the oracle's output (proof bytes, challenges, transcript digest) for three small
+the oracle's output (proof bytes, challenges, transcript digest) for a few small
 instances, so that an unintended change of a byte format or of the oracle's arithmetic
 shows up as a diff; the paper prints no numeric worked example to store instead
 (its protocols are given symbolically: Sec. 2.2, Sec. 3.1, App. A, App. B).
@@ -80,10 +80,26 @@ def aggregate_case():
             "digest_hex": ts.digest().hex()}
 
 
+def reindex_case():
+    """Re-indexing sumcheck (Eq. sc-reindex): stack of N = 4 tensors of D = 8, two sub-stacks."""
+    rng = np.random.default_rng(20230718)
+    x = rng.integers(-50, 50, (4, 8)).astype(np.int64)
+    maps = [[0, 1, 2, 3], [1, 2, 3, -1]]
+    pts = [uniform_fr_limbs(rng, 2).tobytes() for _ in maps]
+    u = uniform_fr_limbs(rng, 3).tobytes()
+    ts = Transcript(11)
+    buf, info = P.reindex_prove(fr_array(x), 4, 8, maps, [list(fr_array_from_le(p, 2)) for p in pts],
+                                list(fr_array_from_le(u, 3)), ts)
+    return {"protocol": "reindex_prove", "cite": "Eq. sc-reindex", "seed": 11, "x": x.reshape(-1).tolist(),
+            "x_shape": [4, 8], "maps": maps, "points_le_hex": [p.hex() for p in pts], "u_le_hex": u.hex(),
+            "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
+
+
 if __name__ == "__main__":
     for name, fn in (("product_k3_d3", product_case), ("matmul_n2_2x4x2", matmul_case),
                      ("matmul_ft_n2_2x4x2", matmul_ft_case),
-                     ("zkrelu_d4_q5_r3", zkrelu_case), ("aggregate_l2_w4_b2_t2", aggregate_case)):
+                     ("zkrelu_d4_q5_r3", zkrelu_case), ("aggregate_l2_w4_b2_t2", aggregate_case),
+                     ("reindex_n4_d8_k2", reindex_case)):
         with open(os.path.join(HERE, name + ".json"), "w") as f:
             json.dump(fn(), f, indent=1)
             f.write("\n")

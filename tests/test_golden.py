@@ -30,13 +30,19 @@ def oracle_run(g):
         buf = P.matmul_ft_prove(fr_array(np.array(g["x0"])), g["x0_shape"], fr_array(np.array(g["x1"])), g["x1_shape"], ts)[0]
     elif g["protocol"] == "zkrelu_prove":
         buf = P.zkrelu_prove(g["Z"], g["GA"], g["Q"], g["R"], ts)[0]
+    elif g["protocol"] == "reindex_prove":
+        n, d = g["x_shape"]
+        pts = [[int(v) for v in fr_array_from_le(bytes.fromhex(h), len(h) // 64)] for h in g["points_le_hex"]]
+        u = [int(v) for v in fr_array_from_le(bytes.fromhex(g["u_le_hex"]), len(g["u_le_hex"]) // 64)]
+        buf = P.reindex_prove(fr_array(np.array(g["x"]).reshape(n, d)), n, d, g["maps"], pts, u, ts)[0]
     else:
         out = P.aggregate_prove(fcnn_window(2307162730 + 90, 2, 4, 2, 2), ts)
         buf = out[0] if isinstance(out, tuple) else out
     return bytes(buf), ts
 
 
-NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "zkrelu_d4_q5_r3", "aggregate_l2_w4_b2_t2"]
+NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "zkrelu_d4_q5_r3", "aggregate_l2_w4_b2_t2",
+         "reindex_n4_d8_k2"]
 
 
 @pytest.mark.parametrize("name", NAMES)
@@ -49,7 +55,7 @@ def test_oracle_reproduces_stored_proofs(name):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("name", NAMES)
+@pytest.mark.parametrize("name", NAMES[:-1])
 def test_library_reproduces_stored_proofs(lib, ctx, name):
     import torch
     g = load(name)
