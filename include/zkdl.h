@@ -179,6 +179,32 @@ int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X
                       zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
                       zkdl_fr* points_out, size_t* npoints);
 
+/* reindex_prove: the re-indexing sumcheck (Sec. 4, Eq. sc-reindex; the re-indexing line of
+ * Protocol zkdl).  X is a stack of N = dim 0 tensors of D = numel / N elements (any kind).
+ * K (1..ZKDL_REINDEX_MAX_K) sub-stacks X_k take tensors of it in their own order:
+ * maps[k] (host, map_len[k] entries, a power of two up to 2^29) holds the stack index of the
+ * j-th tensor of X_k, or -1 for a zero tensor (padding); an index may occur more than once.
+ * Each sub-stack comes with a claim X_k~(points[k], u): points[k] (host, log2 map_len[k]
+ * elements) over its stack axis, u (host, log2 D elements) over the rest.  The call computes
+ * those K claims, draws coefficients r_k, and proves
+ *   sum_k r_k X_k~(points[k], u) = sum_i P[i] X~(i, u),
+ *   P[i] = sum_k r_k sum_{j : maps[k][j] = i} beta~(points[k], j),
+ * by a sumcheck over i on the tables P and X~(., u) (K = 2, degree 2), which leaves the one
+ * claim X~(v, u) on the whole stack; P~(v) is for the verifier to recompute from the maps.
+ * claims (host, K + 2 elements, may be NULL): the K sub-stack claims, P~(v), X~(v, u).
+ * Transcript: "reindex" with the SHA-256 digest of the statement's public part
+ *   u32le N, D, K; per k: u32le map_len[k], the entries as i32le; the points in order k,
+ *   32 B little-endian per element; u;
+ * "c" the K claims; one draw of K coefficients; then the product sumcheck (claim_0, rounds,
+ * finals).  Proof: "ZKRI", N, D, K, the K claims, one SC block.
+ * Errors: ZKDL_EINVAL for a map entry outside [-1, N), sizes that are no powers of two,
+ * D above 2^31 or a points argument that is NULL where elements are needed. */
+#define ZKDL_REINDEX_MAX_K 8
+int reindex_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const int32_t* const* maps,
+                  const uint64_t* map_len, const zkdl_fr* const* points, const zkdl_fr* u,
+                  zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
+                  zkdl_fr* points_out, size_t* npoints);
+
 /* zkrelu_prove: the combined sumcheck of App. A over aux in {0,1}^{2 x D x (Q+R)}
  * (bit axis padded to a power of two), weights r^2, r, 1, r'r^2, r'r, r', then the
  * merge of the three claims on aux into one.  Z, GA: D signed (Q+R)-bit

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
     "mle_partial_eval", "sumcheck_product", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_hadamard",
-    "zkrelu_prove", "aggregate_prove", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
+    "reindex_prove", "zkrelu_prove", "aggregate_prove", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read",
 ]
 
@@ -71,6 +71,7 @@ def load_library():
         "sumcheck_matmul": [vp, vp, vp, i, i, vp, vp, psz, vp, vp, psz],
         "sumcheck_matmul_ft": [vp, vp, vp, i, i, vp, vp, psz, vp, vp, psz],
         "sumcheck_hadamard": [vp, vp, vp, vp, vp, psz, vp, vp, psz],
+        "reindex_prove": [vp, vp, i, pp, C.POINTER(u64), pp, vp, vp, vp, psz, vp, vp, psz],
         "zkrelu_prove": [vp, vp, vp, u64, i, i, i, vp, vp, psz, vp, vp, psz],
         "aggregate_prove": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
         "zkdl_host_fr_mul": [vp, vp, vp], "zkdl_selfcheck_constants": [],
@@ -318,6 +319,23 @@ def sumcheck_hadamard(ctx, x0, x1, tr):
     _check(load_library().sumcheck_hadamard(ctx.handle, x0.handle, x1.handle, tr.handle, o.proof,
                                             C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
            "sumcheck_hadamard", ctx)
+    return o.result()
+
+
+def reindex_prove(ctx, x, maps, points, u, tr):
+    """x: tensor handle of the stack [N, ...]; maps: K sequences of stack indices (-1 = zero
+    tensor); points: K lists of field elements (log2 len(maps[k]) each); u: log2(numel / N)."""
+    k = len(maps)
+    arrs = [np.ascontiguousarray(np.asarray(m, dtype=np.int32)) for m in maps]
+    map_ptrs = (C.c_void_p * k)(*[a.ctypes.data for a in arrs])
+    lens = (C.c_uint64 * k)(*[a.size for a in arrs])
+    pbufs = [C.create_string_buffer(_fr_bytes(p), max(32 * len(p), 1)) for p in points]
+    pt_ptrs = (C.c_void_p * k)(*[C.addressof(b) for b in pbufs])
+    ub = C.create_string_buffer(_fr_bytes(u), max(32 * len(u), 1))
+    o = _Outputs(k + 2)
+    _check(load_library().reindex_prove(ctx.handle, x.handle, k, map_ptrs, lens, pt_ptrs, ub, tr.handle, o.proof,
+                                        C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
+           "reindex_prove", ctx)
     return o.result()
 
 

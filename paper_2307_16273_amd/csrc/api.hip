@@ -852,6 +852,170 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
 }
 
 // ---------------------------------------------------------------------------
+// re-indexing sumcheck (Eq. sc-reindex)
+// ---------------------------------------------------------------------------
+static const uint32_t ZKRI_MAGIC = 0x49524B5Au;
+
+// plain SHA-256 of a byte stream fed in pieces (the transcript's block function, standard padding)
+struct HostSha {
+    ts::State s;
+    HostSha() {
+        const uint32_t iv[8] = {0x6a09e667, 0xbb67ae85, 0x3c6ef372, 0xa54ff53a,
+                                0x510e527f, 0x9b05688c, 0x1f83d9ab, 0x5be0cd19};
+        for (int i = 0; i < 8; ++i) s.h[i] = iv[i];
+        s.nblk = 0;
+        s.fill = 0;
+    }
+    void bytes(const void* p, size_t n) {
+        for (size_t i = 0; i < n; ++i) ts::push_byte(s, ((const uint8_t*)p)[i]);
+    }
+    void u32(uint32_t v) {
+        for (int b = 0; b < 4; ++b) ts::push_byte(s, (uint8_t)(v >> (8 * b)));
+    }
+};
+
+static int upload_bytes(zkdl_ctx* ctx, const void* host, size_t n, void** dev_out) {
+    *dev_out = zk_alloc(ctx, n ? n : 4);
+    if (!*dev_out) return ZKDL_ENOMEM;
+    if (!n) return ZKDL_OK;
+    hipError_t e = hipMemcpyAsync(*dev_out, host, n, hipMemcpyHostToDevice, ctx->stream);
+    if (e != hipSuccess) {
+        ctx->last_hip = (int)e;
+        return ZKDL_EHIP;
+    }
+    return ZKDL_OK;
+}
+
+extern "C" int reindex_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const int32_t* const* maps,
+                             const uint64_t* map_len, const zkdl_fr* const* points, const zkdl_fr* u,
+                             zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
+                             zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !X || !tr || !maps || !map_len || K < 1 || K > ZKDL_REINDEX_MAX_K || X->ndim < 1) return ZKDL_EINVAL;
+    const uint64_t N = X->shape[0], D = X->numel / N;
+    if (!is_pow2(N) || !is_pow2(D) || N > ((uint64_t)1 << 29) || D > ((uint64_t)1 << 31)) return ZKDL_EINVAL;
+    const int ln = ilog2_u64(N), ld = ilog2_u64(D);
+    if (ld > 0 && !u) return ZKDL_EINVAL;
+    uint64_t total = 0;
+    int lk[ZKDL_REINDEX_MAX_K], npts = ld;
+    for (int k = 0; k < K; ++k) {
+        if (!maps[k] || !is_pow2(map_len[k]) || map_len[k] > ((uint64_t)1 << 29)) return ZKDL_EINVAL;
+        lk[k] = ilog2_u64(map_len[k]);
+        if (lk[k] > 0 && (!points || !points[k])) return ZKDL_EINVAL;
+        for (uint64_t j = 0; j < map_len[k]; ++j)
+            if (maps[k][j] < -1 || (int64_t)maps[k][j] >= (int64_t)N) return ZKDL_EINVAL;
+        total += map_len[k];
+        npts += lk[k];
+    }
+    if (total >= ((uint64_t)1 << 32) || K + ln > ZK_MAX_CHAL) return ZKDL_EINVAL;
+
+    // the statement's public part, hashed; all points in one buffer (u first)
+    HostSha hs;
+    hs.u32((uint32_t)N);
+    hs.u32((uint32_t)D);
+    hs.u32((uint32_t)K);
+    for (int k = 0; k < K; ++k) {
+        hs.u32((uint32_t)map_len[k]);
+        for (uint64_t j = 0; j < map_len[k]; ++j) hs.u32((uint32_t)maps[k][j]);
+    }
+    std::vector<uint8_t> pts((size_t)(npts > 0 ? npts : 1) * 32);
+    size_t at = (size_t)ld * 32;
+    if (ld > 0) memcpy(pts.data(), u, (size_t)ld * 32);
+    for (int k = 0; k < K; ++k) {
+        if (lk[k] > 0) memcpy(pts.data() + at, points[k], (size_t)lk[k] * 32);
+        hs.bytes(pts.data() + at, (size_t)lk[k] * 32);
+        at += (size_t)lk[k] * 32;
+    }
+    hs.bytes(pts.data(), (size_t)ld * 32);
+    uint8_t dg[32];
+    ts::digest(hs.s, dg);
+    uint32_t dgw[8];
+    for (int i = 0; i < 8; ++i)
+        dgw[i] = (uint32_t)dg[4 * i] | ((uint32_t)dg[4 * i + 1] << 8) | ((uint32_t)dg[4 * i + 2] << 16) |
+                 ((uint32_t)dg[4 * i + 3] << 24);
+
+    // inverse maps by stack index: counting sort of the (k, j) entries
+    std::vector<uint32_t> row_off(N + 1, 0), ent(total ? total : 1), maps_flat(total ? total : 1);
+    for (int k = 0; k < K; ++k)
+        for (uint64_t j = 0; j < map_len[k]; ++j)
+            if (maps[k][j] >= 0) ++row_off[(size_t)maps[k][j] + 1];
+    for (uint64_t i = 0; i < N; ++i) row_off[i + 1] += row_off[i];
+    {
+        std::vector<uint32_t> cur(row_off.begin(), row_off.end() - 1);
+        uint64_t f = 0;
+        for (int k = 0; k < K; ++k)
+            for (uint64_t j = 0; j < map_len[k]; ++j) {
+                maps_flat[f++] = (uint32_t)maps[k][j];
+                if (maps[k][j] >= 0) ent[cur[(size_t)maps[k][j]]++] = ((uint32_t)k << 29) | (uint32_t)j;
+            }
+    }
+
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    zk_absorb_words(ctx, "reindex", dgw, 8);
+    uint32_t hdr[4] = {ZKRI_MAGIC, (uint32_t)N, (uint32_t)D, (uint32_t)K};
+    zk_write_proof_words(ctx, hdr, 4);
+
+    void *d_pts = nullptr, *d_row = nullptr, *d_ent = nullptr, *d_maps = nullptr;
+    rc = upload_bytes(ctx, pts.data(), (size_t)npts * 32, &d_pts);
+    if (rc == ZKDL_OK) rc = upload_bytes(ctx, row_off.data(), (N + 1) * 4, &d_row);
+    if (rc == ZKDL_OK) rc = upload_bytes(ctx, ent.data(), total * 4, &d_ent);
+    if (rc == ZKDL_OK) rc = upload_bytes(ctx, maps_flat.data(), total * 4, &d_maps);
+    // device memory: Montgomery points | beta_u [D] | beta_k [len k] | T [N] | P [N] | sumcheck work
+    const size_t fr_elems = (size_t)(npts > 0 ? npts : 1) + D + total + 2 * N;
+    void* mem = rc == ZKDL_OK ? zk_alloc(ctx, fr_elems * 32 + zk_sumcheck_work_bytes(2, ln)) : nullptr;
+    if (rc == ZKDL_OK && !mem) rc = ZKDL_ENOMEM;
+    if (rc == ZKDL_OK) {
+        Fr* pm = (Fr*)mem;
+        uint32_t* w = (uint32_t*)mem + 8 * (size_t)(npts > 0 ? npts : 1);
+        if (npts > 0) zk_launch_points_to_mont(ctx, (const uint8_t*)d_pts, npts, pm);
+        BetaJob jobs[ZKDL_REINDEX_MAX_K + 1];
+        ReindexJob job;
+        job.K = K;
+        jobs[0].point = pm;
+        jobs[0].m = ld;
+        jobs[0].out = make_tab(w, D);
+        w += 8 * D;
+        const Fr* pk = pm + ld;
+        const int32_t* mk = (const int32_t*)d_maps;
+        for (int k = 0; k < K; ++k) {
+            jobs[1 + k].point = pk;
+            jobs[1 + k].m = lk[k];
+            jobs[1 + k].out = make_tab(w, map_len[k]);
+            job.map[k] = mk;
+            job.len[k] = map_len[k];
+            job.beta[k] = jobs[1 + k].out;
+            w += 8 * map_len[k];
+            pk += lk[k];
+            mk += map_len[k];
+        }
+        job.row_off = (const uint32_t*)d_row;
+        job.ent = (const uint32_t*)d_ent;
+        const FrTab T = make_tab(w, N);
+        w += 8 * N;
+        const FrTab P = make_tab(w, N);
+        w += 8 * N;
+        rc = zk_build_beta_many(ctx, jobs, K + 1);
+        if (rc == ZKDL_OK) {
+            FrTab xs = make_tab(X->data, X->numel);
+            const void* sp = X->kind == TK_FR ? (const void*)&xs : X->data;
+            rc = zk_partial_eval(ctx, X->kind, sp, N, D, 1, jobs[0].out, T);
+        }
+        if (rc == ZKDL_OK) rc = zk_reindex(ctx, job, T, P, ln, w);
+    }
+    int ids[ZKDL_REINDEX_MAX_K + 2];
+    for (int k = 0; k < K; ++k) ids[k] = 8 + k;
+    ids[K] = 0;
+    ids[K + 1] = 1;
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, K + 2, claims);
+    zk_free(ctx, mem);
+    zk_free(ctx, d_pts);
+    zk_free(ctx, d_row);
+    zk_free(ctx, d_ent);
+    zk_free(ctx, d_maps);
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
+// ---------------------------------------------------------------------------
 // zkReLU and the aggregated proof
 // ---------------------------------------------------------------------------
 static int stage_ints(zkdl_ctx* ctx, const int64_t* host, uint64_t n, void** dev_out) {

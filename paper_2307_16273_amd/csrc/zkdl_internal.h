@@ -146,6 +146,19 @@ void zk_absorb_words(zkdl_ctx* ctx, const char* label, const uint32_t* words, in
 void zk_launch_draw(zkdl_ctx* ctx, int chal_base, int count);
 static inline void zk_flush_frames(zkdl_ctx* ctx) { zk_launch_draw(ctx, 0, 0); }
 
+// ---- k_reindex.hip ---------------------------------------------------------------
+struct ReindexJob {
+    int K;
+    const int32_t* map[ZKDL_REINDEX_MAX_K];   // device: stack index of the j-th tensor of sub-stack k, -1 = zero
+    uint64_t len[ZKDL_REINDEX_MAX_K];
+    FrTab beta[ZKDL_REINDEX_MAX_K];           // beta~(u_k, .)
+    const uint32_t* row_off;                  // device: inverse maps by stack index, 2^ln + 1 offsets into ent
+    const uint32_t* ent;                      // device: k in the top 3 bits, j in the other 29
+};
+// claims of the sub-stacks -> scal[8 ..), absorbed and written to the proof; K coefficients drawn;
+// P built into p; product sumcheck on (p, t) over ln variables, finals at scal[0], scal[1]
+int zk_reindex(zkdl_ctx* ctx, const ReindexJob& job, FrTab t, FrTab p, int ln, void* work_mem);
+
 // ---- k_zkrelu.hip ----------------------------------------------------------------
 // optimized aggregated matrix-product protocol: stack rounds with f_t, then the single-product sumcheck
 int zk_matmul_ft(zkdl_ctx* ctx, const FrTab* src, void* work_mem, int ln, int l2, const FrTab* wsuf, int w_idx,

@@ -55,7 +55,7 @@ def test_oracle_reproduces_stored_proofs(name):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("name", NAMES[:-1])
+@pytest.mark.parametrize("name", NAMES)
 def test_library_reproduces_stored_proofs(lib, ctx, name):
     import torch
     g = load(name)
@@ -68,6 +68,12 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
         x0 = lib.fr_tensor_upload(ctx, np.array(g["x0"], dtype=np.int64), tuple(g["x0_shape"]))
         x1 = lib.fr_tensor_upload(ctx, np.array(g["x1"], dtype=np.int64), tuple(g["x1_shape"]))
         got = getattr(lib, g["protocol"])(ctx, x0, x1, tr)
+    elif g["protocol"] == "reindex_prove":
+        n, d = g["x_shape"]
+        x = lib.fr_tensor_upload(ctx, np.array(g["x"], dtype=np.int64), (n, d))
+        pts = [[int(v) for v in fr_array_from_le(bytes.fromhex(h), len(h) // 64)] for h in g["points_le_hex"]]
+        u = [int(v) for v in fr_array_from_le(bytes.fromhex(g["u_le_hex"]), len(g["u_le_hex"]) // 64)]
+        got = lib.reindex_prove(ctx, x, g["maps"], pts, u, tr)
     elif g["protocol"] == "zkrelu_prove":
         got = lib.zkrelu_prove(ctx, np.array(g["Z"], dtype=np.int64), np.array(g["GA"], dtype=np.int64), tr, g["Q"], g["R"])
     else:

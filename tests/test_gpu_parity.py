@@ -184,6 +184,82 @@ def test_sumcheck_matmul_ft(lib, ctx, n, d1, d2, d3, t0, t1, kind):
     P.matmul_ft_verify(got["proof"], n, d1, d2, d3, OracleTranscript(6))
 
 
+def _reindex_maps(case, n):
+    rng = np.random.default_rng(99)
+    if case == "layers":          # inputs of the layers / their outputs: a shift by one tensor
+        return [list(range(0, n // 2)), list(range(1, n // 2 + 1))]
+    if case == "shift_pad":
+        return [list(range(n)), list(range(1, n)) + [-1]]
+    if case == "single":
+        return [[0]]
+    if case == "swap":
+        return [[1, 0], [0, -1]]
+    if case == "repeat":
+        return [[7, 6, 5, 4, 3, 2, 1, 0], [2, 5], [0, 0, 3, -1]]
+    # "random8": eight maps of mixed lengths with repeats and padding
+    maps = []
+    for k in range(8):
+        m = rng.integers(-1, n, max(n >> k, 1))
+        maps.append([int(v) for v in m])
+    return maps
+
+
+@pytest.mark.parametrize("n,d,case,kind", [
+    (4, 8, "shift_pad", "i32"),
+    (8, 4, "repeat", "fr"),
+    (1, 2, "single", "fr"),
+    (2, 1, "swap", "i64"),
+    (32, 4096, "layers", "i32"),
+    (4096, 64, "random8", "i32"),      # 12 rounds over the stack: two grid rounds, then the single-block tail
+])
+def test_reindex_prove(lib, ctx, n, d, case, kind):
+    """Re-indexing sumcheck (Eq. sc-reindex): proof bytes, challenges, claims and transcript
+    against the oracle; the oracle's verifier accepts the library's proof."""
+    import torch
+    say(f"reindex_prove N={n} D={d} {case} {kind}")
+    rng = np.random.default_rng(n * 7 + d)
+    maps = _reindex_maps(case, n)
+    if kind == "fr":
+        raw = uniform_fr_limbs(rng, n * d).tobytes()
+        x = lib.fr_tensor_upload(ctx, raw, (n, d))
+        fx = fr_array_from_le(raw, n * d)
+    elif kind == "i32":
+        xi = rng.integers(-2 ** 31, 2 ** 31, (n, d), dtype=np.int64).astype(np.int32)
+        x = lib.tensor_wrap_int(ctx, torch.from_numpy(xi).cuda())
+        fx = fr_array(xi)
+    else:
+        xi = rng.integers(-2 ** 63, 2 ** 63, (n, d), dtype=np.int64)
+        x = lib.fr_tensor_upload(ctx, xi, (n, d))
+        fx = fr_array(xi)
+    points = [[int(v) for v in fr_array_from_le(rand_fr_bytes(300 + k, 32), 32)[:len(m).bit_length() - 1]]
+              for k, m in enumerate(maps)]
+    u = [int(v) for v in fr_array_from_le(rand_fr_bytes(299, 40), 40)[:d.bit_length() - 1]]
+    tr = lib.Transcript(12)
+    got = lib.reindex_prove(ctx, x, maps, points, u, tr)
+    ots = OracleTranscript(12)
+    buf, info = P.reindex_prove(fx, n, d, maps, points, u, ots)
+    assert got["proof"] == buf
+    assert got["points"] == ots.challenges
+    assert got["claims"] == info["claims"] + info["inner"].finals
+    assert tr.digest() == ots.digest()
+    claims, vs, xw = P.reindex_verify(got["proof"], n, d, maps, points, u, OracleTranscript(12))
+    assert xw == got["claims"][-1]
+
+
+def test_reindex_prove_rejects_bad_arguments(lib, ctx):
+    say("reindex_prove argument checks")
+    x = lib.fr_tensor_upload(ctx, np.arange(8, dtype=np.int64), (4, 2))
+    tr = lib.Transcript(1)
+    before = tr.digest()
+    for maps, points in (([[0, 4]], [[5]]),              # index beyond the stack
+                         ([[0, -2]], [[5]]),             # below -1
+                         ([[0, 1, 2]], [[5, 6]]),        # length no power of two
+                         ([[0]] * 9, [[]] * 9)):         # too many sub-stacks
+        with pytest.raises(lib.ZkdlError):
+            lib.reindex_prove(ctx, x, maps, points, [3], tr)
+    assert tr.digest() == before
+
+
 @pytest.mark.parametrize("shape", [(1,), (2, 4, 4), (4, 64, 16)])
 def test_sumcheck_hadamard(lib, ctx, shape):
     say(f"sumcheck_hadamard shape={shape}")
