@@ -15,8 +15,8 @@
 //    equality factor splits as beta~(u_bin,(i,j)) = beta_I(i) beta_J(j).
 //    Rounds 0, 1 and 2 work on the integers directly: aux is binary, so in round 0
 //    a(x)^2 - a(x) = (x^2 - x) [bit_lo != bit_hi]; after the first challenge an
-//    entry is one of {0, 1, v, 1-v}, which makes round 1 a table look-up by bit masks
-//    (bin1_body); after the second it is one of 16 values and a pair one of 256
+//    entry is one of {0, 1, v, 1-v} and round 1 a quadratic form in bits: masked sums of
+//    beta_J and five products (bin1_body); after the second it is one of 16 values and a pair one of 256
 //    combinations, so round 2 reads q(x) from a 256-entry table (bin2_body).
 //    After the third challenge the columns are written out once (k_zk_mat3, one of
 //    256 values per entry), column-major: entry (k, j, i) at plane (k*(Q+R)+j), so
@@ -438,12 +438,11 @@ __device__ __forceinline__ void bin0_body(const BinArgs& a, const unsigned bx, c
 // aux is binary, so after binding x0 = v0 an entry is one of four values, selected by the
 // two bits it interpolates: A(b_lo, b_hi) = b_lo + v0 (b_hi - b_lo), code = b_lo + 2 b_hi:
 //   code 0 -> 0, 1 -> 1 - v0, 2 -> v0, 3 -> 1.
-// Round 1 (variable x1) pairs two such entries: 16 combinations, and for each the binarity
-// summand q(x) = e(x)^2 - e(x), e(x) = A_lo + x (A_hi - A_lo), is a constant of the round.
-// So round 1 needs no table in memory at all: per (i, slice) the columns are grouped by
-// combination with bit masks, S_c = sum of beta_J over the columns of combination c, and the
-// contribution is sum_c Q_x[c] S_c: 16 products instead of 48.  After v1 the entry is one of
-// 16 values (k_zk_mat2 writes them out, D/4 rows); later rounds fold as usual.
+// Round 1 (variable x1) pairs two such entries; its summand is a quadratic form in the four bits
+// that an entry pair interpolates, with coefficients that are constants of the round, so the
+// round needs no table in memory at all: sums of beta_J over column sets chosen by the bits, and
+// five products per (i, slice) (bin1_body).  After v1 the entry is one of 16 values (k_zk_mat2
+// writes them out, D/4 rows); later rounds fold as usual.
 
 __device__ __forceinline__ F9Tab aux_col9(const BinArgs& a, int k, int j) {
     F9Tab t;
@@ -472,26 +471,78 @@ __device__ __forceinline__ void beta_line_fold(const BinArgs& a, uint64_t b, uin
     e[2] = f9_norm(f9_add(e[1], dn));
 }
 
-// Round 1 by look-up.  m = D/4 quadruples (i'', i''+m | i''+2m, i''+3m) = (x0, x1) in
-// {(0,0), (0,1), (1,0), (1,1)}.  Writes partial sums for x = 0, 2, 3 (x = 1 comes from the claim).
+// Sums of beta_J over column sets by table: the columns are cut into groups of BJ_BITS and
+// tab[g][e] holds the sum of beta_J(BJ_BITS g + i) over the set bits i of e (normal, below
+// BJ_BITS r), so a masked sum is one table entry per group and the same work for every lane.
+constexpr int BJ_BITS = 7;
+constexpr int BJ_MAXG = (64 + BJ_BITS - 1) / BJ_BITS;
+constexpr int BJ_TAB_WORDS = BJ_MAXG * (1 << BJ_BITS) * 9;
+
+// sbj: beta_J as lazy limbs (64 entries, zero beyond nbits); all threads of the block
+__device__ __forceinline__ void bj_tables_build(uint32_t* tab, const F9* sbj, int groups) {
+    for (int idx = threadIdx.x; idx < groups << BJ_BITS; idx += blockDim.x) {
+        const int g = idx >> BJ_BITS, e = idx & ((1 << BJ_BITS) - 1);
+        F9 s = f9_zero();
+#pragma unroll
+        for (int i = 0; i < BJ_BITS; ++i)
+            if (((e >> i) & 1) && BJ_BITS * g + i < 64) s = f9_add(s, sbj[BJ_BITS * g + i]);
+        s = f9_norm(s);
+#pragma unroll
+        for (int l = 0; l < 9; ++l) tab[idx * 9 + l] = s.v[l];
+    }
+}
+
+// sum of beta_J over the set bits of mask: normal, below 64 r
+__device__ __forceinline__ F9 bj_masked_sum(const uint32_t* tab, uint64_t mask, int groups) {
+    F9 s = f9_zero();
+#pragma unroll
+    for (int g = 0; g < BJ_MAXG; ++g) {
+        if (g < groups) {
+            const uint32_t* e = tab + ((g << BJ_BITS) + (uint32_t)((mask >> (BJ_BITS * g)) & ((1u << BJ_BITS) - 1))) * 9;
+#pragma unroll
+            for (int l = 0; l < 9; ++l) s.v[l] += e[l];
+        }
+        if (g == 6) s = f9_norm(s);   // seven entries with limbs below 2^29 each so far
+    }
+    s = f9_norm(s);
+    // keep the scheduler from starting the next sum's loads before this one is consumed: with
+    // several sums in flight the registers run out
+    __builtin_amdgcn_sched_barrier(0);
+    return s;
+}
+
+// Round 1 on the integers.  m = D/4 quadruples of rows (i'', i''+m | i''+2m, i''+3m) = (x0, x1) in
+// {(0,0), (0,1), (1,0), (1,1)}; bit j of row (x0, x1) is B_{x0,x1}(j).  With x0 bound to v0 the
+// entry that the round interpolates is
+//   e_j(X) = sum_{x0,x1} chi_{x0} w_{x1}(X) B_{x0,x1}(j),  chi = (1 - v0, v0),  w(X) = (1 - X, X),
+// a combination of bits whose coefficients add up to one, hence
+//   e^2 - e = - sum over unordered pairs of rows of (coefficient product) [the two bits differ].
+// Summed over the columns with beta_J that is
+//   sum_j beta_J(j) q_j(X) = -[(1-X)^2 A + X^2 C + X(1-X) B],
+//   A = chi0 chi1 S(B00 ^ B10),  C = chi0 chi1 S(B01 ^ B11),
+//   B = chi0^2 S(B00 ^ B01) + chi0 chi1 (S(B00 ^ B11) + S(B10 ^ B01)) + chi1^2 S(B10 ^ B11),
+// S(mask) = sum of beta_J over the set bits: six masked sums and five products per
+// (quadruple, slice), whatever the bits are.  A and C are accumulated with the negated constant
+// (A' = -A, C' = -C): G(0) = A', G(2) = A' + 4 C' + 2 B, G(3) = 4 A' + 9 C' + 6 B.  Writes partial sums for x = 0, 2, 3
+// (x = 1 comes from the claim).
 __device__ __forceinline__ void bin1_body(const BinArgs& a, const unsigned bx, const unsigned gx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ F9 sbj[64];
-    __shared__ F9 qx[2][3][16];   // [slice][x in {0,2,3}][combination]; slice 1 carries r'
+    __shared__ uint32_t bjt[BJ_TAB_WORDS];
+    __shared__ F9 kc[2][4];   // [slice][-chi0 chi1, chi0^2, chi0 chi1, chi1^2]; slice 1 carries r'
     const int tid = threadIdx.x;
+    const int groups = (a.nbits + BJ_BITS - 1) / BJ_BITS;
     if (tid < 64) sbj[tid] = tid < a.nbits ? fr_unpack(a.bJ[tid]) : f9_zero();
-    if (tid < 48) {
-        const int c = tid & 15, xi = tid >> 4;
-        const Fr v0 = *a.chal, one = fr_one();
-        const Fr alo = bit_pair_value(c & 3, v0, one), ahi = bit_pair_value(c >> 2, v0, one);
-        const Fr d = fr_sub(ahi, alo);
-        Fr e = alo;                                   // x = 0
-        if (xi >= 1) e = fr_add(fr_add(alo, d), d);   // x = 2
-        if (xi == 2) e = fr_add(e, d);                // x = 3
-        const Fr q = fr_sub(fr_sqr(e), e);
-        qx[0][xi][c] = fr_unpack(q);
-        qx[1][xi][c] = fr_unpack(fr_mul(*a.rp, q));
+    if (tid >= 64 && tid < 72) {
+        const int k = (tid - 64) >> 2, q = (tid - 64) & 3;
+        const Fr v0 = *a.chal, u0 = fr_sub(fr_one(), v0);
+        Fr c = q == 1 ? fr_sqr(u0) : q == 3 ? fr_sqr(v0) : fr_mul(u0, v0);
+        if (q == 0) c = fr_neg(c);
+        if (k == 1) c = fr_mul(*a.rp, c);
+        kc[k][q] = fr_unpack(c);
     }
+    __syncthreads();
+    bj_tables_build(bjt, sbj, groups);
     __syncthreads();
     const uint64_t m = a.m;
     const F9 vprev9 = fr_unpack(*a.vprev);
@@ -500,44 +551,56 @@ __device__ __forceinline__ void bin1_body(const BinArgs& a, const unsigned bx, c
 #pragma unroll
     for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
     for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
-        // sum over the combinations of Q_x[c] S_c as 64-bit columns: one reduction per (i'', x)
-        uint64_t cols[3][17];
+        // rows of the quadruple, both slices
+        uint64_t w[2][4];
 #pragma unroll
-        for (int x = 0; x < 3; ++x)
-#pragma unroll
-            for (int c = 0; c < 17; ++c) cols[x][c] = 0;
-        int pending = 0;
-        for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+        for (int k = 0; k < 2; ++k) {
             const int64_t* src = k == 0 ? a.z : a.ga;
-            // (x0, x1): w00 = (0,0), w01 = (0,1), w10 = (1,0), w11 = (1,1)
-            const uint64_t w00 = (uint64_t)src[b], w01 = (uint64_t)src[b + m];
-            const uint64_t w10 = (uint64_t)src[b + 2 * m], w11 = (uint64_t)src[b + 3 * m];
-            for (int c = 1; c < 15; ++c) {   // q = 0 for c = 0, 15: both entries are the same bit
-                // lo entry (x1 = 0) interpolates bits (w00, w10); hi entry (x1 = 1) bits (w01, w11)
-                uint64_t mask = keep;
-                mask &= (c & 1) ? w00 : ~w00;
-                mask &= (c & 2) ? w10 : ~w10;
-                mask &= (c & 4) ? w01 : ~w01;
-                mask &= (c & 8) ? w11 : ~w11;
-                if (mask == 0) continue;
-                const F9 s = masked_sum9(sbj, mask);             // value < 64 r, normal
 #pragma unroll
-                for (int x = 0; x < 3; ++x) f9_cols_mac(cols[x], qx[k][x][c], s);
-                if (++pending == 4) {
-                    pending = 0;
+            for (int q = 0; q < 4; ++q) w[k][q] = (k == 0 || a.has_ga) ? (uint64_t)src[b + q * m] & keep : 0;
+        }
+        // w[k][0] = B00, [1] = B01, [2] = B10, [3] = B11 (x0 selects the half, x1 the quarter).
+        // Every masked sum is normal and below 64 r; one accumulator at a time.
+        F9 red3[3];   // A', C', B
 #pragma unroll
-                    for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
+        for (int t = 0; t < 3; ++t) {
+            uint64_t cols[17];
+#pragma unroll
+            for (int c = 0; c < 17; ++c) cols[c] = 0;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                if (k == 1 && !a.has_ga) break;
+                if (t == 0) {
+                    f9_cols_mac(cols, kc[k][0], bj_masked_sum(bjt, w[k][0] ^ w[k][2], groups));
+                } else if (t == 1) {
+                    f9_cols_mac(cols, kc[k][0], bj_masked_sum(bjt, w[k][1] ^ w[k][3], groups));
+                } else {
+                    f9_cols_mac(cols, kc[k][1], bj_masked_sum(bjt, w[k][0] ^ w[k][1], groups));
+                    const F9 cross = f9_norm(f9_add(bj_masked_sum(bjt, w[k][0] ^ w[k][3], groups),
+                                                    bj_masked_sum(bjt, w[k][2] ^ w[k][1], groups)));
+                    f9_cols_mac(cols, kc[k][2], cross);
+                    f9_cols_mac(cols, kc[k][3], bj_masked_sum(bjt, w[k][2] ^ w[k][3], groups));
+                    f9_cols_norm<17>(cols);
                 }
             }
+            f9_cols_norm<17>(cols);
+            red3[t] = f9_redc(cols);
+            __builtin_amdgcn_sched_barrier(0);
         }
         F9 bi[3];
         beta_line_fold(a, b, m, vprev9, bi);
-#pragma unroll
-        for (int x = 0; x < 3; ++x) {
-            // at most 28 products below 64 r^2 each: the reduced sum is below 27 r, normal
-            f9_cols_norm<17>(cols[x]);
-            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_redc(cols[x]))));
-        }
+        // sums of at most 6 products below 128 r^2: the reduced values are normal and below 12 r
+        const F9 ra = red3[0], rc = red3[1], rb = red3[2];
+        // limbs of ra, rb, rc are below 2^29: at most eight of them are added between carry passes
+        const F9 c2 = f9_add(rc, rc), c4 = f9_add(c2, c2), b2 = f9_add(rb, rb), a2 = f9_add(ra, ra);
+        const F9 g2 = f9_norm(f9_add(f9_add(ra, c4), b2));                 // A' + 4 C' + 2 B
+        const F9 t1 = f9_norm(f9_add(f9_add(a2, a2), c4));                 // 4 A' + 4 C'
+        const F9 t2 = f9_norm(f9_add(f9_add(c4, rc), b2));                 // 5 C' + 2 B
+        const F9 t3 = f9_norm(f9_add(b2, b2));                             // 4 B
+        const F9 g3 = f9_norm(f9_add(f9_add(t1, t2), t3));                 // 4 A' + 9 C' + 6 B
+        tot[0] = f9_norm_reduce(f9_add(tot[0], f9_mul(bi[0], ra)));
+        tot[1] = f9_norm_reduce(f9_add(tot[1], f9_mul(bi[1], g2)));
+        tot[2] = f9_norm_reduce(f9_add(tot[2], f9_mul(bi[2], g3)));
     }
     {
         const Fr s = block_sum_lazy<3>(tot, red);
