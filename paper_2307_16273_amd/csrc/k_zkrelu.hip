@@ -67,7 +67,8 @@ struct PrepArgs {
     uint64_t D;
     int nbits, r_bits;
     ZkBeta8 beta;        // packed equality tables, read
-    ZkTabs tabs;         // value tables, written
+    ZkTabs tabs;         // value tables, written if write_vals
+    int write_vals;      // 0: the first two i-rounds read the integers themselves
     Fr* part;            // per block: 4 partial dot products
     DevState* st;
 };
@@ -85,9 +86,11 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_prepare(PrepArgs a) {
         bool neg = (z >> (a.nbits - 1)) & 1;            // aux(0, i, Q+R-1)
         int64_t zp = rescale_half_up(z, a.r_bits);
         Fr fz = fr_from_i64(z), fzp = fr_from_i64(zp);
-        f9tab_st(a.tabs.t[T_Z], i, fr_unpack(fz));
-        f9tab_st(a.tabs.t[T_ZP], i, fr_unpack(fzp));
-        f9tab_st(a.tabs.t[T_NS], i, fr_unpack(neg ? fr_zero() : fr_one()));
+        if (a.write_vals) {
+            f9tab_st(a.tabs.t[T_Z], i, fr_unpack(fz));
+            f9tab_st(a.tabs.t[T_ZP], i, fr_unpack(fzp));
+            f9tab_st(a.tabs.t[T_NS], i, fr_unpack(neg ? fr_zero() : fr_one()));
+        }
         acc[0] = fr_add(acc[0], fr_mul(tab_ld(a.beta.t[0], i), fz));
         if (!neg) acc[1] = fr_add(acc[1], fr_mul(tab_ld(a.beta.t[1], i), fzp));
         if (a.ga) {
@@ -95,8 +98,10 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_prepare(PrepArgs a) {
             bad |= !in_range(g, a.nbits);
             int64_t gp = rescale_half_up(g, a.r_bits);
             Fr fg = fr_from_i64(g), fgp = fr_from_i64(gp);
-            f9tab_st(a.tabs.t[T_GA], i, fr_unpack(fg));
-            f9tab_st(a.tabs.t[T_GAP], i, fr_unpack(fgp));
+            if (a.write_vals) {
+                f9tab_st(a.tabs.t[T_GA], i, fr_unpack(fg));
+                f9tab_st(a.tabs.t[T_GAP], i, fr_unpack(fgp));
+            }
             acc[2] = fr_add(acc[2], fr_mul(tab_ld(a.beta.t[2], i), fg));
             if (!neg) acc[3] = fr_add(acc[3], fr_mul(tab_ld(a.beta.t[3], i), fgp));
         }
@@ -180,6 +185,12 @@ struct LinArgs {
     const Fr* chal;
     Fr* part;
     int has_ga;
+    // rounds 0 and 1 on the integers (from_ints): the value tables Z, Z', 1 - sign, G_A, G_A' do
+    // not exist yet; round 1 writes them, folded, for the later rounds
+    int from_ints;
+    const int64_t* z;
+    const int64_t* ga;
+    int nbits, r_bits;
 };
 
 // pair (lo, hi) of a lazy table, folded with the previous challenge first when FOLD; both
@@ -260,6 +271,271 @@ __device__ __forceinline__ void lin_body(const LinArgs& a, const unsigned bx, co
         }
     }
     {   // thread j holds the sum for x = 0, 2, 3; g(1) is derived from the claim
+        const Fr s = block_sum_lazy<3>(acc, red);
+        Fr* pp = a.part + (uint64_t)bx * 4;
+        if (threadIdx.x < 3) pp[threadIdx.x ? threadIdx.x + 1 : 0] = s;
+        else if (threadIdx.x == 3) pp[1] = fr_zero();
+    }
+}
+
+// ---- rounds 0 and 1 of the linear equations on the integers --------------------------------
+// The value tables hold integers of at most 56 bits (Z, G_A), their rescaled values and the bit
+// 1 - sign.  A table entry in Montgomery form times a plain integer is the Montgomery form of the
+// product, so in round 0 a term  (weight beta)(x) * value(x)  is a 9-limb by 2-limb product with no
+// reduction: the lines of the value tables through x = 0, 2, 3 are integers below 2^58 in
+// magnitude.  The products are accumulated as 64-bit columns (11 of them) and reduced once per
+// thread.  Round 1 binds v0 on the way: a + v0 (a' - a) for integers a, a' is
+// redc(R^2 |a| +- v0 R^2 |a' - a|), one reduction and no full product; the folded tables are written
+// out for the later rounds, which work on field elements as before.
+
+// cols += c * mag for a normal or negated-normal c (limbs below 2^30.6) and mag < 2^58
+__device__ __forceinline__ void cols11_mac(uint64_t* cols, const F9& c, uint64_t mag) {
+    const uint32_t m0 = (uint32_t)mag & frc::M29, m1 = (uint32_t)(mag >> 29);
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+        cols[i] += (uint64_t)c.v[i] * m0;
+        cols[i + 1] += (uint64_t)c.v[i] * m1;
+    }
+}
+
+// cols += p * c for a signed c, |c| < 2^58, and a normal p below 2.6 r: a negative c turns p
+// into 4r - p
+__device__ __forceinline__ void cols11_mac_signed(uint64_t* cols, const F9& p, int64_t c) {
+    const bool neg = c < 0;
+    const uint64_t mag = neg ? (uint64_t)0 - (uint64_t)c : (uint64_t)c;
+    F9 q;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) q.v[i] = neg ? frc::C4R[i] - p.v[i] : p.v[i];
+    cols11_mac(cols, q, mag);
+}
+
+// lo + x (hi - lo) at x = 0, 2, 3, each normal and below 2.41 r
+__device__ __forceinline__ void line3_reduced(const F9& lo, const F9& hi, F9 e[3]) {
+    const F9 dn = f9_norm(f9_sub(hi, lo));
+    e[0] = lo;
+    e[1] = f9_norm_reduce(f9_add(hi, dn));
+    e[2] = f9_norm_reduce(f9_add(e[1], dn));
+}
+
+struct IntRow {
+    int64_t z, zp, ns;
+};
+__device__ __forceinline__ IntRow int_row(int64_t z, int nbits, int r_bits) {
+    IntRow r;
+    r.z = z;
+    r.zp = rescale_half_up(z, r_bits);
+    r.ns = 1 - ((z >> (nbits - 1)) & 1);
+    return r;
+}
+
+// carries of an 11-column accumulator: columns 0..9 below 2^29 afterwards
+__device__ __forceinline__ void cols11_carry(uint64_t* cols) {
+#pragma unroll
+    for (int k = 0; k + 1 < 11; ++k) {
+        cols[k + 1] += cols[k] >> 29;
+        cols[k] &= frc::M29;
+    }
+}
+
+// carried 11-column sum V -> lazy value congruent to it, normal and below 2.41 r:
+// V = low nine limbs + 2^261 * high part, and 2^261 is the Montgomery radix, so the high part
+// times R^2 as a Montgomery product is congruent to 2^261 * high part
+__device__ __forceinline__ F9 cols11_value(const uint64_t* cols) {
+    F9 vlo, vhi = f9_zero();
+#pragma unroll
+    for (int i = 0; i < 9; ++i) vlo.v[i] = (uint32_t)cols[i];
+    vhi.v[0] = (uint32_t)cols[9];
+    vhi.v[1] = (uint32_t)cols[10] & frc::M29;
+    vhi.v[2] = (uint32_t)(cols[10] >> 29) & frc::M29;
+    vhi.v[3] = (uint32_t)(cols[10] >> 58);
+    return f9_norm_reduce(f9_add(vlo, f9_mul(vhi, fr_unpack(fr_const(frc::R2)))));
+}
+
+// The four input claims from the integers (same bounds as round 0 below): dot products of the
+// equality tables as built with Z, (1 - sign) Z', G_A, (1 - sign) G_A'; also the range check.
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_prepare_int(PrepArgs a) {
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    uint64_t cols[4][11];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int c = 0; c < 11; ++c) cols[q][c] = 0;
+    bool bad = false;
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < a.D;
+         i += (uint64_t)gridDim.x * blockDim.x) {
+        const int64_t z = a.z[i];
+        bad |= !in_range(z, a.nbits);
+        const IntRow rz = int_row(z, a.nbits, a.r_bits);
+        cols11_mac_signed(cols[0], fr_unpack(tab_ld(a.beta.t[0], i)), rz.z);
+        cols11_mac_signed(cols[1], fr_unpack(tab_ld(a.beta.t[1], i)), rz.ns * rz.zp);
+        cols11_carry(cols[0]);
+        cols11_carry(cols[1]);
+        if (a.ga) {
+            const int64_t g = a.ga[i];
+            bad |= !in_range(g, a.nbits);
+            cols11_mac_signed(cols[2], fr_unpack(tab_ld(a.beta.t[2], i)), g);
+            cols11_mac_signed(cols[3], fr_unpack(tab_ld(a.beta.t[3], i)), rz.ns * rescale_half_up(g, a.r_bits));
+            cols11_carry(cols[2]);
+            cols11_carry(cols[3]);
+        }
+    }
+    if (bad) atomicOr(&a.st->err, 1u);
+    F9 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = cols11_value(cols[q]);
+    const Fr s = block_sum_lazy<4>(acc, red);
+    if (threadIdx.x < 4) a.part[(uint64_t)blockIdx.x * 4 + threadIdx.x] = s;
+}
+
+// Round 0.  Bounds: |Z| < 2^55, so a line value |3 hi - 2 lo| < 2^57.4; |Z'| <= 2^54, the line of
+// 1 - sign is within [-2, 3]: their product is below 2^58.
+__device__ __forceinline__ void lin0_int_body(const LinArgs& a, const unsigned bx, const unsigned gx) {
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    uint64_t cols[3][11];
+#pragma unroll
+    for (int x = 0; x < 3; ++x)
+#pragma unroll
+        for (int c = 0; c < 11; ++c) cols[x][c] = 0;
+    const uint64_t m = a.m;
+    for (uint64_t b = bx * (uint64_t)blockDim.x + threadIdx.x; b < m; b += (uint64_t)gx * blockDim.x) {
+        const IntRow zl = int_row(a.z[b], a.nbits, a.r_bits), zh = int_row(a.z[b + m], a.nbits, a.r_bits);
+        int64_t nsq[3];
+        F9 lo, hi, p[3];
+#pragma unroll
+        for (int x = 0; x < 3; ++x) nsq[x] = zl.ns + (x ? x + 1 : 0) * (zh.ns - zl.ns);
+        lo = f9tab_ld(a.tabs.t[T_BZ], b);
+        hi = f9tab_ld(a.tabs.t[T_BZ], b + m);
+        line3_reduced(lo, hi, p);
+#pragma unroll
+        for (int x = 0; x < 3; ++x) cols11_mac_signed(cols[x], p[x], zl.z + (x ? x + 1 : 0) * (zh.z - zl.z));
+        lo = f9tab_ld(a.tabs.t[T_BA], b);
+        hi = f9tab_ld(a.tabs.t[T_BA], b + m);
+        line3_reduced(lo, hi, p);
+#pragma unroll
+        for (int x = 0; x < 3; ++x)
+            cols11_mac_signed(cols[x], p[x], nsq[x] * (zl.zp + (x ? x + 1 : 0) * (zh.zp - zl.zp)));
+        if (a.has_ga) {
+            const IntRow gl = int_row(a.ga[b], a.nbits, a.r_bits), gh = int_row(a.ga[b + m], a.nbits, a.r_bits);
+            lo = f9tab_ld(a.tabs.t[T_BGA], b);
+            hi = f9tab_ld(a.tabs.t[T_BGA], b + m);
+            line3_reduced(lo, hi, p);
+#pragma unroll
+            for (int x = 0; x < 3; ++x) cols11_mac_signed(cols[x], p[x], gl.z + (x ? x + 1 : 0) * (gh.z - gl.z));
+            lo = f9tab_ld(a.tabs.t[T_BGZ], b);
+            hi = f9tab_ld(a.tabs.t[T_BGZ], b + m);
+            line3_reduced(lo, hi, p);
+#pragma unroll
+            for (int x = 0; x < 3; ++x)
+                cols11_mac_signed(cols[x], p[x], nsq[x] * (gl.zp + (x ? x + 1 : 0) * (gh.zp - gl.zp)));
+        }
+        // four terms of two products below 2^59.6 per column, then the carries
+#pragma unroll
+        for (int x = 0; x < 3; ++x) cols11_carry(cols[x]);
+    }
+    F9 acc[3];
+#pragma unroll
+    for (int x = 0; x < 3; ++x) acc[x] = cols11_value(cols[x]);
+    const Fr s = block_sum_lazy<3>(acc, red);
+    Fr* pp = a.part + (uint64_t)bx * 4;
+    if (threadIdx.x < 3) pp[threadIdx.x ? threadIdx.x + 1 : 0] = s;
+    else if (threadIdx.x == 3) pp[1] = fr_zero();
+}
+
+// a0 + v0 (a2 - a0) in Montgomery form from the integers; k = (R^2, -R^2, v0 R^2, -v0 R^2),
+// canonical.  Four products below 2^58 per column; the result is normal and below 2 r.
+__device__ __forceinline__ F9 fold_ints(const F9* k, int64_t a0, int64_t a2) {
+    const int64_t d = a2 - a0;
+    const bool n0 = a0 < 0, nd = d < 0;
+    uint64_t cols[17];
+#pragma unroll
+    for (int c = 0; c < 17; ++c) cols[c] = 0;
+    F9 c0, cd;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+        c0.v[i] = n0 ? k[1].v[i] : k[0].v[i];
+        cd.v[i] = nd ? k[3].v[i] : k[2].v[i];
+    }
+    cols11_mac(cols, c0, n0 ? (uint64_t)0 - (uint64_t)a0 : (uint64_t)a0);
+    cols11_mac(cols, cd, nd ? (uint64_t)0 - (uint64_t)d : (uint64_t)d);
+    return f9_redc(cols);
+}
+
+// Round 1: binds v0 while reading; the equality tables fold as field elements, the value tables
+// from the integers; both are written out folded (length 2m).
+__device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned bx, const unsigned gx) {
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    __shared__ F9 kf[4];     // R^2, -R^2, v0 R^2, -v0 R^2
+    __shared__ F9 kns[4];    // 1 - sign folded, by (bit at x0 = 0) + 2 (bit at x0 = 1): 0, 1 - v0, v0, 1
+    if (threadIdx.x < 4) {
+        const Fr v0 = *a.chal, r2 = fr_const(frc::R2), one = fr_one();
+        const Fr c = threadIdx.x < 2 ? r2 : fr_mul(v0, r2);
+        kf[threadIdx.x] = fr_unpack((threadIdx.x & 1) ? fr_neg(c) : c);
+        kns[threadIdx.x] = fr_unpack(threadIdx.x == 0 ? fr_zero() : threadIdx.x == 1 ? fr_sub(one, v0)
+                                     : threadIdx.x == 2 ? v0 : one);
+    }
+    __syncthreads();
+    F9 acc[3];
+#pragma unroll
+    for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
+    const F9 v = fr_unpack(*a.chal);
+    const uint64_t m = a.m;
+    for (uint64_t b = bx * (uint64_t)blockDim.x + threadIdx.x; b < m; b += (uint64_t)gx * blockDim.x) {
+        F9 lo, hi, ns[3], p[3], q[3];
+        IntRow r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = int_row(a.z[b + i * m], a.nbits, a.r_bits);
+        // rows b, b + 2m fold into lo; b + m, b + 3m into hi
+        lo = kns[(int)(r[0].ns + 2 * r[2].ns)];
+        hi = kns[(int)(r[1].ns + 2 * r[3].ns)];
+        f9tab_st(a.tabs.t[T_NS], b, lo);
+        f9tab_st(a.tabs.t[T_NS], b + m, hi);
+        line3<false>(lo, hi, ns);
+        lin_pair<true>(a.tabs.t[T_BZ], b, m, v, lo, hi);
+        line3<true>(lo, hi, p);
+        lo = fold_ints(kf, r[0].z, r[2].z);
+        hi = fold_ints(kf, r[1].z, r[3].z);
+        f9tab_st(a.tabs.t[T_Z], b, lo);
+        f9tab_st(a.tabs.t[T_Z], b + m, hi);
+        line3<false>(lo, hi, q);
+#pragma unroll
+        for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
+        lin_pair<true>(a.tabs.t[T_BA], b, m, v, lo, hi);
+        line3<true>(lo, hi, p);
+        lo = fold_ints(kf, r[0].zp, r[2].zp);
+        hi = fold_ints(kf, r[1].zp, r[3].zp);
+        f9tab_st(a.tabs.t[T_ZP], b, lo);
+        f9tab_st(a.tabs.t[T_ZP], b + m, hi);
+        line3<false>(lo, hi, q);
+#pragma unroll
+        for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(f9_mul(p[x], ns[x]), q[x]));
+#pragma unroll
+        for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
+        if (a.has_ga) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = int_row(a.ga[b + i * m], a.nbits, a.r_bits);
+            lin_pair<true>(a.tabs.t[T_BGA], b, m, v, lo, hi);
+            line3<true>(lo, hi, p);
+            lo = fold_ints(kf, r[0].z, r[2].z);
+            hi = fold_ints(kf, r[1].z, r[3].z);
+            f9tab_st(a.tabs.t[T_GA], b, lo);
+            f9tab_st(a.tabs.t[T_GA], b + m, hi);
+            line3<false>(lo, hi, q);
+#pragma unroll
+            for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
+            lin_pair<true>(a.tabs.t[T_BGZ], b, m, v, lo, hi);
+            line3<true>(lo, hi, p);
+            lo = fold_ints(kf, r[0].zp, r[2].zp);
+            hi = fold_ints(kf, r[1].zp, r[3].zp);
+            f9tab_st(a.tabs.t[T_GAP], b, lo);
+            f9tab_st(a.tabs.t[T_GAP], b + m, hi);
+            line3<false>(lo, hi, q);
+#pragma unroll
+            for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(f9_mul(p[x], ns[x]), q[x]));
+#pragma unroll
+            for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
+        }
+    }
+    {
         const Fr s = block_sum_lazy<3>(acc, red);
         Fr* pp = a.part + (uint64_t)bx * 4;
         if (threadIdx.x < 3) pp[threadIdx.x ? threadIdx.x + 1 : 0] = s;
@@ -924,7 +1200,10 @@ struct ZkRoundArgs {
 template <int MODE>
 __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     if (blockIdx.x < a.nb_lin) {
-        if (a.lin_small) lin_body_small<MODE != 0>(a.lin, blockIdx.x);
+        if (MODE <= 1 && a.lin.from_ints) {
+            if (MODE == 0) lin0_int_body(a.lin, blockIdx.x, a.nb_lin);
+            else lin1_int_body(a.lin, blockIdx.x, a.nb_lin);
+        } else if (a.lin_small) lin_body_small<MODE != 0>(a.lin, blockIdx.x);
         else lin_body<MODE != 0>(a.lin, blockIdx.x, a.nb_lin);
         return;
     }
@@ -1332,10 +1611,15 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     pa.r_bits = R;
     pa.beta = beta8;
     pa.tabs = tabs;
+    // the first two i-rounds of the linear equations read the integers (they must exist, and
+    // the line values must fit 58 bits)
+    const int lin_from_ints = li >= 2 && nbits <= 56;
+    pa.write_vals = !lin_from_ints;
     pa.part = ctx->partials;
     pa.st = st;
     unsigned nb = blocks_for(D, ZK_MAX_PART_BLOCKS);
-    hipLaunchKernelGGL(k_zk_prepare, dim3(nb), dim3(ZK_BLOCK), 0, ctx->stream, pa);
+    if (lin_from_ints) hipLaunchKernelGGL(k_zk_prepare_int, dim3(nb), dim3(ZK_BLOCK), 0, ctx->stream, pa);
+    else hipLaunchKernelGGL(k_zk_prepare, dim3(nb), dim3(ZK_BLOCK), 0, ctx->stream, pa);
     ClaimsArgs ca;
     ca.part = ctx->partials;
     ca.nblk = (int)nb;
@@ -1373,8 +1657,13 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         ra.lin.chal = t > 0 ? &st->chal[c_v + t - 1] : nullptr;
         ra.lin.part = ctx->partials;
         ra.lin.has_ga = has_ga;
+        ra.lin.from_ints = lin_from_ints && t <= 1;
+        ra.lin.z = z_dev;
+        ra.lin.ga = ga_dev;
+        ra.lin.nbits = nbits;
+        ra.lin.r_bits = R;
         // few pairs: 16 per block, spread over (table, pair) and (point, equation, pair) threads
-        ra.lin_small = m <= (uint64_t)LIN_SMALL_PAIRS * (ZK_MAX_PART_BLOCKS / 2);
+        ra.lin_small = !ra.lin.from_ints && m <= (uint64_t)LIN_SMALL_PAIRS * (ZK_MAX_PART_BLOCKS / 2);
         const unsigned nb_lin = ra.lin_small ? (unsigned)((m + LIN_SMALL_PAIRS - 1) / LIN_SMALL_PAIRS)
                                              : blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
         ra.nb_lin = nb_lin;

@@ -296,6 +296,8 @@ def test_chained_calls_share_one_transcript(lib, ctx):
 ZKRELU_CASES = [
     (1, True, 32, 16), (2, True, 32, 16), (4, False, 32, 16), (64, True, 32, 16),
     (16, True, 5, 3), (8, True, 4, 4), (4, True, 48, 16), (512, False, 32, 16), (1024, True, 32, 16),
+    (1024, True, 48, 16),      # 64 bit planes: the first rounds read the value tables, not the integers
+    (256, True, 40, 16),       # 56 bit planes: the widest integers the first rounds take themselves
 ]
 
 
@@ -315,6 +317,26 @@ def test_zkrelu(lib, ctx, d_len, with_ga, q, r):
     assert got["points"] == ots.challenges
     assert got["proof"] == buf
     assert got["claims"] == info["c_in"]
+    assert tr.digest() == ots.digest()
+
+
+@pytest.mark.parametrize("q,r", [(40, 16), (32, 16), (55, 1)])
+def test_zkrelu_extreme_values(lib, ctx, q, r):
+    """Every entry at an end of the (Q+R)-bit range, arranged so that the pairs and quadruples
+    of the first two rounds see opposite ends: the integer lines reach their largest magnitude."""
+    say(f"zkrelu extremes Q={q} R={r}")
+    lim = 1 << (q + r - 1)
+    d_len = 32
+    pat = np.array([lim - 1, -lim], dtype=np.int64)
+    z = pat[(np.arange(d_len) // 8 + np.arange(d_len) // 16 + np.arange(d_len)) % 2]
+    ga = pat[(np.arange(d_len) // 16 + 1 + np.arange(d_len) // 4) % 2]
+    z[5], ga[7] = 0, -1
+    tr = lib.Transcript(22)
+    got = lib.zkrelu_prove(ctx, z, ga, tr, q, r)
+    ots = OracleTranscript(22)
+    buf, info = P.zkrelu_prove(z.tolist(), ga.tolist(), q, r, ots)
+    assert got["proof"] == buf
+    assert got["points"] == ots.challenges
     assert tr.digest() == ots.digest()
 
 
