@@ -1067,6 +1067,169 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat3(BinArgs a) {
     }
 }
 
+// ---- round 3 from the integers; the columns are written after the fourth challenge -------
+// With three challenges bound an entry is one of 256 values A[c] (c: its eight bits, as in
+// k_zk_mat3).  Round 3 pairs two of them, 65 536 combinations: too many for a table of q(x), but
+//   q(X) = e(X)^2 - e(X) = (1 - X) p(lo) + X p(hi) - X (1 - X) (hi - lo)^2,   p(a) = a^2 - a,
+// and p(lo), p(hi) are table entries too (P[c] = A[c]^2 - A[c]): one square per column instead
+// of three, and no column in memory yet.  Per pair index the sums over the columns
+//   SA = sum beta_J p(lo), SC = sum beta_J p(hi), SD = sum beta_J (hi - lo)^2
+// are accumulated as 64-bit columns; G(0) = SA, G(2) = -SA + 2 SC + 2 SD, G(3) = -2 SA + 3 SC + 6 SD.
+// The rows of pair index i4 (m = D/16 of them) are i4 + s m, s = 8 x0 + 4 x1 + 2 x2 + x3.
+
+// A[c] for the 256 codes: lazy limbs, normal, below 2.41 r; limb-major in LDS
+__device__ __forceinline__ void bound3_values(const Fr* chal, F9* val16, uint32_t (*alut)[256]) {
+    bound2_values(chal, val16);
+    __syncthreads();
+    const int tid = threadIdx.x;
+    const F9 v2 = fr_unpack(chal[2]);
+    const F9 lo = val16[tid & 15], hi = val16[tid >> 4];
+    const F9 f = f9_norm_reduce(f9_add(lo, f9_mul(f9_sub(hi, lo), v2)));
+#pragma unroll
+    for (int l = 0; l < 9; ++l) alut[l][tid] = f.v[l];
+}
+
+__device__ __forceinline__ F9 lut9(const uint32_t (*lut)[256], uint32_t c) {
+    F9 f;
+#pragma unroll
+    for (int l = 0; l < 9; ++l) f.v[l] = lut[l][c];
+    return f;
+}
+
+// codes of the two entries that bit j of the sixteen rows w[s] gives: even rows (x3 = 0) and
+// odd rows (x3 = 1), each in the bit order of pair_code8
+__device__ __forceinline__ void pair_codes16(const uint64_t w[16], int j, uint32_t& clo, uint32_t& chi) {
+    uint64_t e[8], o[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        e[s] = w[2 * s] >> j;
+        o[s] = w[2 * s + 1] >> j;
+    }
+    clo = pair_code8(e);
+    chi = pair_code8(o);
+}
+
+__device__ __forceinline__ void bin3_body(const BinArgs& a, const unsigned bx, const unsigned by, const unsigned gx) {
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    __shared__ F9 sbj[2][64];
+    __shared__ F9 val16[16];
+    __shared__ uint32_t alut[9][256];   // A[c]
+    __shared__ uint32_t plut[9][256];   // A[c]^2 - A[c]
+    const int tid = threadIdx.x;
+    if (tid < 128) {
+        const int j = tid & 63, k = tid >> 6;
+        F9 x = f9_zero();
+        if (j < a.nbits) x = fr_unpack(k == 0 ? a.bJ[j] : fr_mul(*a.rp, a.bJ[j]));
+        sbj[k][j] = x;
+    }
+    bound3_values(a.chal, val16, alut);
+    {
+        const F9 one9 = fr_unpack(fr_one());
+        const F9 f = lut9(alut, tid);
+        const F9 q = f9_mul(f, f9_sub(f, one9));      // normal, below 2 r
+#pragma unroll
+        for (int l = 0; l < 9; ++l) plut[l][tid] = q.v[l];
+    }
+    __syncthreads();
+    const uint64_t m = a.m;
+    const F9 vprev9 = fr_unpack(*a.vprev);
+    const unsigned chunk = a.ksplit ? by >> 1 : by;
+    const int k0 = a.ksplit ? (int)(by & 1) : 0, k1 = a.ksplit ? k0 + 1 : (a.has_ga ? 2 : 1);
+    int j0 = chunk * a.jc, j1 = j0 + a.jc;
+    if (j1 > a.nbits) j1 = a.nbits;
+    F9 tot[3];
+#pragma unroll
+    for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
+    for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
+        uint64_t cols[3][17];   // SA, SC, SD
+#pragma unroll
+        for (int x = 0; x < 3; ++x)
+#pragma unroll
+            for (int c = 0; c < 17; ++c) cols[x][c] = 0;
+        int pending = 0;
+        for (int k = k0; k < k1; ++k) {
+            const int64_t* src = k == 0 ? a.z : a.ga;
+            uint64_t w[16];
+#pragma unroll
+            for (int s2 = 0; s2 < 16; ++s2) w[s2] = (uint64_t)src[b + (uint64_t)s2 * m];
+            for (int j = j0; j < j1; ++j) {
+                uint32_t clo, chi;
+                pair_codes16(w, j, clo, chi);
+                const F9 bj = sbj[k][j];
+                f9_cols_mac(cols[0], bj, lut9(plut, clo));
+                f9_cols_mac(cols[1], bj, lut9(plut, chi));
+                const F9 d = f9_norm(f9_sub(lut9(alut, chi), lut9(alut, clo)));   // normal, below 6.5 r
+                f9_cols_mac(cols[2], bj, f9_mul(d, d));
+                if (++pending == 4) {
+                    pending = 0;
+#pragma unroll
+                    for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
+                }
+            }
+        }
+        F9 bi[3];
+        beta_line_fold(a, b, m, vprev9, bi);
+#pragma unroll
+        for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
+        // at most 128 products below 2 r^2 each: the reduced sums are normal and below 4.8 r;
+        // below, at most eight such limbs are added between carry passes, and what is
+        // subtracted is below 2.6 r after f9_norm_reduce
+        const F9 sa = f9_norm_reduce(f9_redc(cols[0])), sc = f9_redc(cols[1]), sd = f9_redc(cols[2]);
+        const F9 sc2 = f9_add(sc, sc), sd2 = f9_add(sd, sd);
+        const F9 g2 = f9_norm(f9_sub(f9_add(sc2, sd2), sa));                             // -SA + 2 SC + 2 SD
+        const F9 h3 = f9_norm(f9_add(f9_add(sc2, sc), f9_add(sd2, sd2)));                // 3 SC + 4 SD
+        const F9 g3 = f9_norm(f9_sub(f9_sub(f9_add(h3, sd2), sa), sa));                  // ... + 2 SD - 2 SA
+        tot[0] = f9_norm_reduce(f9_add(tot[0], f9_mul(bi[0], sa)));
+        tot[1] = f9_norm_reduce(f9_add(tot[1], f9_mul(bi[1], g2)));
+        tot[2] = f9_norm_reduce(f9_add(tot[2], f9_mul(bi[2], g3)));
+    }
+    const uint64_t blk = (uint64_t)by * gx + bx;
+    {
+        const Fr s = block_sum_lazy<3>(tot, red);
+        Fr* p = a.part + blk * 4;
+        if (tid < 3) p[tid ? tid + 1 : 0] = s;
+        else if (tid == 3) p[1] = fr_zero();
+    }
+}
+
+// After the fourth challenge: entry (k, v0..v3, i4, j) = (1 - v3) A[c_lo] + v3 A[c_hi]: two table
+// reads and an addition; written as lazy limbs (normal, below 2 r), D/16 rows per column.
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat4(BinArgs a) {
+    __shared__ F9 val16[16];
+    __shared__ uint32_t alut[9][256];
+    __shared__ uint32_t lut0[9][256];   // (1 - v3) A[c], fully reduced
+    __shared__ uint32_t lut1[9][256];   // v3 A[c], fully reduced
+    const int tid = threadIdx.x;
+    bound3_values(a.chal, val16, alut);
+    {
+        const Fr v3 = a.chal[3], u3 = fr_sub(fr_one(), v3);
+        const F9 f = lut9(alut, tid);
+        const F9 f0 = f9_cond_sub(f9_mul(fr_unpack(u3), f)), f1 = f9_cond_sub(f9_mul(fr_unpack(v3), f));
+#pragma unroll
+        for (int l = 0; l < 9; ++l) {
+            lut0[l][tid] = f0.v[l];
+            lut1[l][tid] = f1.v[l];
+        }
+    }
+    __syncthreads();
+    const uint64_t m = a.m;   // rows written = D / 16
+    int j0 = blockIdx.y * a.jc, j1 = j0 + a.jc;
+    if (j1 > a.nbits) j1 = a.nbits;
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+        for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+            const int64_t* src = k == 0 ? a.z : a.ga;
+            uint64_t w[16];
+#pragma unroll
+            for (int s2 = 0; s2 < 16; ++s2) w[s2] = (uint64_t)src[b + (uint64_t)s2 * m];
+            for (int j = j0; j < j1; ++j) {
+                uint32_t clo, chi;
+                pair_codes16(w, j, clo, chi);
+                f9tab_st(aux_col9(a, k, j), b, f9_norm(f9_add(lut9(lut0, clo), lut9(lut1, chi))));
+            }
+        }
+    }
+}
+
 // the raw entries of one column that a pair index needs: (b, b+m), or (b, b+m, b+2m, b+3m)
 // when the previous challenge is still to be bound
 template <bool FOLD>
@@ -1195,7 +1358,7 @@ struct ZkRoundArgs {
     int lin_small;         // the linear blocks take LIN_SMALL_PAIRS pairs each
 };
 
-// MODE 0: first round; 1, 2: look-up rounds on the integers; 3: first round on the columns
+// MODE 0: first round; 1, 2, 5: rounds 1, 2, 3 on the integers; 3: first round on the columns
 // in memory; 4: later rounds (fold the columns with the previous challenge first)
 template <int MODE>
 __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
@@ -1212,6 +1375,7 @@ __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     if (MODE == 0) bin0_body(a.bin, bx, a.bin_gx);
     else if (MODE == 1) bin1_body(a.bin, bx, a.bin_gx);
     else if (MODE == 2) bin2_body(a.bin, bx, by, a.bin_gx);
+    else if (MODE == 5) bin3_body(a.bin, bx, by, a.bin_gx);
     else binl_body<MODE == 4>(a.bin, bx, by, a.bin_gx);
 }
 
@@ -1549,9 +1713,9 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     zk_launch_draw(ctx, c0, 5 * li + lj);
 
     // memory: 10 D-sized tables, beta_J, aux columns (2 * nbits columns of 36 B entries; the rows
-    // are written once three challenges are bound, D/8 of them; two challenges if D = 4)
-    const int mat_bound = li >= 3 ? 3 : 2;
-    const uint64_t rows = li >= 3 ? D / 8 : 1;
+    // are written once four challenges are bound, D/16 of them; fewer challenges if D < 16)
+    const int mat_bound = li >= 4 ? 4 : li >= 3 ? 3 : 2;
+    const uint64_t rows = li >= 3 ? D >> mat_bound : 1;
     const uint64_t aux_elems = (uint64_t)(has_ga ? 2 : 1) * nbits * rows;
     const uint64_t alt_rows = D >= 2 ? D / 2 : 1;   // second buffer of the beta_I folds
     void* mem = zk_alloc(ctx, (uint64_t)LIN_TABLES * D * 36 + 64 * 32 + alt_rows * 36 + (li >= 2 ? aux_elems * 36 : 0));
@@ -1689,7 +1853,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         const unsigned bx = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / chunks);
         const unsigned nb_bin = bx * chunks;
         ba.jc = jc;
-        ba.chal = t == 0 ? nullptr : t <= 2 ? &st->chal[c_v] : t >= 4 ? &st->chal[c_v + t - 1] : nullptr;
+        ba.chal = t == 0 ? nullptr : t < mat_bound ? &st->chal[c_v] : t > mat_bound ? &st->chal[c_v + t - 1] : nullptr;
         ra.bin = ba;
         ra.bin_gx = bx;
         // algorithmic bytes: the linear tables (9 of them with G_A, 5 without) and beta_I in 36-byte
@@ -1699,12 +1863,14 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         if (t == 0) bytes += ns * 16.0 * (double)m;
         else if (t == 1) bytes += ns * 32.0 * (double)m;
         else if (t == 2) bytes += ns * 64.0 * (double)m;
-        else bytes += ns * nbits * (t >= 4 ? 216.0 : 72.0) * (double)m;
+        else if (t < mat_bound) bytes += ns * 128.0 * (double)m;
+        else bytes += ns * nbits * (t > mat_bound ? 216.0 : 72.0) * (double)m;
         zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, bytes);
         if (t == 0) launch_zk_round<0>(ctx, ra, nb_bin);
         else if (t == 1) launch_zk_round<1>(ctx, ra, nb_bin);
         else if (t == 2) launch_zk_round<2>(ctx, ra, nb_bin);
-        else if (t == 3) launch_zk_round<3>(ctx, ra, nb_bin);
+        else if (t < mat_bound) launch_zk_round<5>(ctx, ra, nb_bin);
+        else if (t == mat_bound) launch_zk_round<3>(ctx, ra, nb_bin);
         else launch_zk_round<4>(ctx, ra, nb_bin);
         zk_prof_end(ctx);
         // g(1) is taken from the running claim: the binarity kernels leave it out
@@ -1720,6 +1886,8 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
             ba.m = m;
             if (mat_bound == 2)
                 hipLaunchKernelGGL(k_zk_mat2, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            else if (mat_bound == 4)
+                hipLaunchKernelGGL(k_zk_mat4, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
             else
                 hipLaunchKernelGGL(k_zk_mat3, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
         }
