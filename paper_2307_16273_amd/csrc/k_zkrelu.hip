@@ -47,6 +47,54 @@ struct ZkBeta8 {
     FrTab t[5];
 };
 
+// An equality table over i in two factors: beta~(u, i) = H[i >> lb] L[i & (2^lb - 1)], H over the
+// leading variables of u and L over the others.  While the variables that the rounds bind lie in
+// H, the table over i is never built: an entry is one product of two entries of tables of about
+// sqrt(D) elements, which stay in cache, and binding a challenge folds H alone.  The first two
+// i-rounds work this way; round 1 writes the folded tables (D/2 entries) for the later rounds.
+struct SplitEq {
+    F9Tab H[5], L[5];   // Z, A, G_A, G_Z (times the weights of their equations once those are drawn), I
+    int lb;
+};
+
+__device__ __forceinline__ F9 split_entry(const F9Tab& H, const F9Tab& L, int lb, uint64_t i) {
+    // factors normal and below 2.41 r: the product is normal and below 2 r
+    return f9_mul(f9tab_ld(H, i >> lb), f9tab_ld(L, i & (((uint64_t)1 << lb) - 1)));
+}
+
+struct SplitConvArgs {
+    FrTab src[10];     // packed tables as built: H of the five points, then L
+    F9Tab dst[10];
+    uint64_t n[10];
+};
+
+// packed -> lazy limbs, table blockIdx.y
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_split_convert(SplitConvArgs a) {
+    const int q = blockIdx.y;
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < a.n[q]; i += (uint64_t)gridDim.x * blockDim.x)
+        f9tab_st(a.dst[q], i, fr_unpack(tab_ld(a.src[q], i)));
+}
+
+// H of the four linear equations times the weight of the equation (in place), once r, r' are drawn
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_split_scale(SplitEq sp, uint64_t nh, const Fr* weights, int has_ga) {
+    const int e = blockIdx.y;
+    if (e >= 2 && !has_ga) return;
+    const F9 w = fr_unpack(weights[e]);
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < nh; i += (uint64_t)gridDim.x * blockDim.x)
+        f9tab_st(sp.H[e], i, f9_cond_sub(f9_mul(f9tab_ld(sp.H[e], i), w)));
+}
+
+// binds the leading variable of the five H tables: dst[j] = src[j] + v (src[j + half] - src[j])
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_split_fold(SplitEq src, SplitEq dst, uint64_t half, const Fr* v, int has_ga) {
+    const int e = blockIdx.y;
+    if ((e == 2 || e == 3) && !has_ga) return;
+    const F9 v9 = fr_unpack(*v);
+    for (uint64_t j = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; j < half; j += (uint64_t)gridDim.x * blockDim.x) {
+        const F9 lo = f9tab_ld(src.H[e], j), hi = f9tab_ld(src.H[e], j + half);
+        f9tab_st(dst.H[e], j, f9_norm_reduce(f9_add(lo, f9_mul(f9_sub(hi, lo), v9))));
+    }
+}
+
 __device__ __forceinline__ int64_t rescale_half_up(int64_t x, int r_bits) {
     // floor((x + 2^(R-1)) / 2^R) without overflow
     return ((x >> (r_bits - 1)) + 1) >> 1;
@@ -69,6 +117,7 @@ struct PrepArgs {
     ZkBeta8 beta;        // packed equality tables, read
     ZkTabs tabs;         // value tables, written if write_vals
     int write_vals;      // 0: the first two i-rounds read the integers themselves
+    SplitEq sp;          // k_zk_prepare_int: the equality tables in two factors, as built
     Fr* part;            // per block: 4 partial dot products
     DevState* st;
 };
@@ -191,6 +240,7 @@ struct LinArgs {
     const int64_t* z;
     const int64_t* ga;
     int nbits, r_bits;
+    SplitEq sp;            // with from_ints: the equality tables in two factors (H bound as far as the round needs)
 };
 
 // pair (lo, hi) of a lazy table, folded with the previous challenge first when FOLD; both
@@ -366,15 +416,15 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_prepare_int(PrepArgs a) {
         const int64_t z = a.z[i];
         bad |= !in_range(z, a.nbits);
         const IntRow rz = int_row(z, a.nbits, a.r_bits);
-        cols11_mac_signed(cols[0], fr_unpack(tab_ld(a.beta.t[0], i)), rz.z);
-        cols11_mac_signed(cols[1], fr_unpack(tab_ld(a.beta.t[1], i)), rz.ns * rz.zp);
+        cols11_mac_signed(cols[0], split_entry(a.sp.H[0], a.sp.L[0], a.sp.lb, i), rz.z);
+        cols11_mac_signed(cols[1], split_entry(a.sp.H[1], a.sp.L[1], a.sp.lb, i), rz.ns * rz.zp);
         cols11_carry(cols[0]);
         cols11_carry(cols[1]);
         if (a.ga) {
             const int64_t g = a.ga[i];
             bad |= !in_range(g, a.nbits);
-            cols11_mac_signed(cols[2], fr_unpack(tab_ld(a.beta.t[2], i)), g);
-            cols11_mac_signed(cols[3], fr_unpack(tab_ld(a.beta.t[3], i)), rz.ns * rescale_half_up(g, a.r_bits));
+            cols11_mac_signed(cols[2], split_entry(a.sp.H[2], a.sp.L[2], a.sp.lb, i), g);
+            cols11_mac_signed(cols[3], split_entry(a.sp.H[3], a.sp.L[3], a.sp.lb, i), rz.ns * rescale_half_up(g, a.r_bits));
             cols11_carry(cols[2]);
             cols11_carry(cols[3]);
         }
@@ -403,26 +453,26 @@ __device__ __forceinline__ void lin0_int_body(const LinArgs& a, const unsigned b
         F9 lo, hi, p[3];
 #pragma unroll
         for (int x = 0; x < 3; ++x) nsq[x] = zl.ns + (x ? x + 1 : 0) * (zh.ns - zl.ns);
-        lo = f9tab_ld(a.tabs.t[T_BZ], b);
-        hi = f9tab_ld(a.tabs.t[T_BZ], b + m);
+        lo = split_entry(a.sp.H[0], a.sp.L[0], a.sp.lb, b);
+        hi = split_entry(a.sp.H[0], a.sp.L[0], a.sp.lb, b + m);
         line3_reduced(lo, hi, p);
 #pragma unroll
         for (int x = 0; x < 3; ++x) cols11_mac_signed(cols[x], p[x], zl.z + (x ? x + 1 : 0) * (zh.z - zl.z));
-        lo = f9tab_ld(a.tabs.t[T_BA], b);
-        hi = f9tab_ld(a.tabs.t[T_BA], b + m);
+        lo = split_entry(a.sp.H[1], a.sp.L[1], a.sp.lb, b);
+        hi = split_entry(a.sp.H[1], a.sp.L[1], a.sp.lb, b + m);
         line3_reduced(lo, hi, p);
 #pragma unroll
         for (int x = 0; x < 3; ++x)
             cols11_mac_signed(cols[x], p[x], nsq[x] * (zl.zp + (x ? x + 1 : 0) * (zh.zp - zl.zp)));
         if (a.has_ga) {
             const IntRow gl = int_row(a.ga[b], a.nbits, a.r_bits), gh = int_row(a.ga[b + m], a.nbits, a.r_bits);
-            lo = f9tab_ld(a.tabs.t[T_BGA], b);
-            hi = f9tab_ld(a.tabs.t[T_BGA], b + m);
+            lo = split_entry(a.sp.H[2], a.sp.L[2], a.sp.lb, b);
+            hi = split_entry(a.sp.H[2], a.sp.L[2], a.sp.lb, b + m);
             line3_reduced(lo, hi, p);
 #pragma unroll
             for (int x = 0; x < 3; ++x) cols11_mac_signed(cols[x], p[x], gl.z + (x ? x + 1 : 0) * (gh.z - gl.z));
-            lo = f9tab_ld(a.tabs.t[T_BGZ], b);
-            hi = f9tab_ld(a.tabs.t[T_BGZ], b + m);
+            lo = split_entry(a.sp.H[3], a.sp.L[3], a.sp.lb, b);
+            hi = split_entry(a.sp.H[3], a.sp.L[3], a.sp.lb, b + m);
             line3_reduced(lo, hi, p);
 #pragma unroll
             for (int x = 0; x < 3; ++x)
@@ -460,8 +510,8 @@ __device__ __forceinline__ F9 fold_ints(const F9* k, int64_t a0, int64_t a2) {
     return f9_redc(cols);
 }
 
-// Round 1: binds v0 while reading; the equality tables fold as field elements, the value tables
-// from the integers; both are written out folded (length 2m).
+// Round 1: v0 is bound on the way; the equality tables come from their two factors (H already
+// folded), the value tables from the integers; both are written out folded (length 2m).
 __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned bx, const unsigned gx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ F9 kf[4];     // R^2, -R^2, v0 R^2, -v0 R^2
@@ -477,7 +527,6 @@ __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned b
     F9 acc[3];
 #pragma unroll
     for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
-    const F9 v = fr_unpack(*a.chal);
     const uint64_t m = a.m;
     for (uint64_t b = bx * (uint64_t)blockDim.x + threadIdx.x; b < m; b += (uint64_t)gx * blockDim.x) {
         F9 lo, hi, ns[3], p[3], q[3];
@@ -490,7 +539,10 @@ __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned b
         f9tab_st(a.tabs.t[T_NS], b, lo);
         f9tab_st(a.tabs.t[T_NS], b + m, hi);
         line3<false>(lo, hi, ns);
-        lin_pair<true>(a.tabs.t[T_BZ], b, m, v, lo, hi);
+        lo = split_entry(a.sp.H[0], a.sp.L[0], a.sp.lb, b);
+        hi = split_entry(a.sp.H[0], a.sp.L[0], a.sp.lb, b + m);
+        f9tab_st(a.tabs.t[T_BZ], b, lo);
+        f9tab_st(a.tabs.t[T_BZ], b + m, hi);
         line3<true>(lo, hi, p);
         lo = fold_ints(kf, r[0].z, r[2].z);
         hi = fold_ints(kf, r[1].z, r[3].z);
@@ -499,7 +551,10 @@ __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned b
         line3<false>(lo, hi, q);
 #pragma unroll
         for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
-        lin_pair<true>(a.tabs.t[T_BA], b, m, v, lo, hi);
+        lo = split_entry(a.sp.H[1], a.sp.L[1], a.sp.lb, b);
+        hi = split_entry(a.sp.H[1], a.sp.L[1], a.sp.lb, b + m);
+        f9tab_st(a.tabs.t[T_BA], b, lo);
+        f9tab_st(a.tabs.t[T_BA], b + m, hi);
         line3<true>(lo, hi, p);
         lo = fold_ints(kf, r[0].zp, r[2].zp);
         hi = fold_ints(kf, r[1].zp, r[3].zp);
@@ -513,7 +568,10 @@ __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned b
         if (a.has_ga) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) r[i] = int_row(a.ga[b + i * m], a.nbits, a.r_bits);
-            lin_pair<true>(a.tabs.t[T_BGA], b, m, v, lo, hi);
+            lo = split_entry(a.sp.H[2], a.sp.L[2], a.sp.lb, b);
+        hi = split_entry(a.sp.H[2], a.sp.L[2], a.sp.lb, b + m);
+        f9tab_st(a.tabs.t[T_BGA], b, lo);
+        f9tab_st(a.tabs.t[T_BGA], b + m, hi);
             line3<true>(lo, hi, p);
             lo = fold_ints(kf, r[0].z, r[2].z);
             hi = fold_ints(kf, r[1].z, r[3].z);
@@ -522,7 +580,10 @@ __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned b
             line3<false>(lo, hi, q);
 #pragma unroll
             for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
-            lin_pair<true>(a.tabs.t[T_BGZ], b, m, v, lo, hi);
+            lo = split_entry(a.sp.H[3], a.sp.L[3], a.sp.lb, b);
+        hi = split_entry(a.sp.H[3], a.sp.L[3], a.sp.lb, b + m);
+        f9tab_st(a.tabs.t[T_BGZ], b, lo);
+        f9tab_st(a.tabs.t[T_BGZ], b + m, hi);
             line3<true>(lo, hi, p);
             lo = fold_ints(kf, r[0].zp, r[2].zp);
             hi = fold_ints(kf, r[1].zp, r[3].zp);
@@ -640,6 +701,9 @@ struct BinArgs {
     int ksplit;            // column chunk = by / 2 and slice = by % 2 (few rows: more threads)
     const Fr* bJ;          // J entries
     const Fr* rp;          // r'
+    int split;             // rounds 0, 1: beta_I(i) = sH[i >> s_lb] sL[i & (2^s_lb - 1)] (sH bound as far as needed)
+    F9Tab sH, sL;
+    int s_lb;
     Fr* part;              // partials of this kernel
 };
 
@@ -693,7 +757,14 @@ __device__ __forceinline__ void bin0_body(const BinArgs& a, const unsigned bx, c
             c = f9_add(c, masked_sum9(sbj[1], dg));          // limbs below 2^30
         }
         // round 0: the table is as built, fully reduced; line at x = 2, 3, normal
-        const F9 lo = f9tab_ld(a.bI, b), hi = f9tab_ld(a.bI, b + m);
+        F9 lo, hi;
+        if (a.split) {
+            lo = split_entry(a.sH, a.sL, a.s_lb, b);
+            hi = split_entry(a.sH, a.sL, a.s_lb, b + m);
+        } else {
+            lo = f9tab_ld(a.bI, b);
+            hi = f9tab_ld(a.bI, b + m);
+        }
         const F9 dn = f9_norm(f9_sub(hi, lo));
         const F9 b2 = f9_norm(f9_add(hi, dn)), b3 = f9_norm(f9_add(b2, dn));
         acc[0] = f9_norm_reduce(f9_add(acc[0], f9_mul(b2, c)));
@@ -735,10 +806,16 @@ __device__ __forceinline__ Fr bit_pair_value(int code, const Fr& v, const Fr& on
 // variable (length 4m); bind the previous challenge, leave the folded pair in the other buffer
 // for the next round (every column chunk writes the same values), return the line at 0, 2, 3
 __device__ __forceinline__ void beta_line_fold(const BinArgs& a, uint64_t b, uint64_t m, const F9& vprev, F9 e[3]) {
-    const F9 t0 = f9tab_ld(a.bI, b), t1 = f9tab_ld(a.bI, b + m);
-    const F9 t2 = f9tab_ld(a.bI, b + 2 * m), t3 = f9tab_ld(a.bI, b + 3 * m);
-    const F9 lo = f9_norm_reduce(f9_add(t0, f9_mul(f9_sub(t2, t0), vprev)));
-    const F9 hi = f9_norm_reduce(f9_add(t1, f9_mul(f9_sub(t3, t1), vprev)));
+    F9 lo, hi;
+    if (a.split) {   // round 1: the H factor is folded already
+        lo = split_entry(a.sH, a.sL, a.s_lb, b);
+        hi = split_entry(a.sH, a.sL, a.s_lb, b + m);
+    } else {
+        const F9 t0 = f9tab_ld(a.bI, b), t1 = f9tab_ld(a.bI, b + m);
+        const F9 t2 = f9tab_ld(a.bI, b + 2 * m), t3 = f9tab_ld(a.bI, b + 3 * m);
+        lo = f9_norm_reduce(f9_add(t0, f9_mul(f9_sub(t2, t0), vprev)));
+        hi = f9_norm_reduce(f9_add(t1, f9_mul(f9_sub(t3, t1), vprev)));
+    }
     f9tab_st(a.bI_out, b, lo);
     f9tab_st(a.bI_out, b + m, hi);
     const F9 dn = f9_norm(f9_sub(hi, lo));
@@ -1719,7 +1796,15 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     const uint64_t aux_elems = (uint64_t)(has_ga ? 2 : 1) * nbits * rows;
     const uint64_t alt_rows = D >= 2 ? D / 2 : 1;   // second buffer of the beta_I folds
     void* mem = zk_alloc(ctx, (uint64_t)LIN_TABLES * D * 36 + 64 * 32 + alt_rows * 36 + (li >= 2 ? aux_elems * 36 : 0));
-    void* beta_mem = zk_alloc(ctx, (uint64_t)5 * D * 32);
+    // the first two i-rounds read the integers and take the equality tables over i as products
+    // of two factors (the integers must exist in round 1, and the line values must fit 58 bits);
+    // otherwise the five tables are built whole
+    const int split = li >= 2 && nbits <= 56;
+    const int hb = li / 2, lb = li - hb;
+    const uint64_t nh = (uint64_t)1 << hb, nl = (uint64_t)1 << lb;
+    // split: packed H and L of the five points, then as lazy limbs H, H folded once, L
+    const uint64_t split_words = 5 * (nh + nl) * 8 + 5 * (nh + (nh + 1) / 2 + nl) * 9;
+    void* beta_mem = zk_alloc(ctx, split ? split_words * 4 : (uint64_t)5 * D * 32);
     if (!mem || !beta_mem) {
         zk_free(ctx, mem);
         zk_free(ctx, beta_mem);
@@ -1741,21 +1826,58 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     uint32_t* aux = base;
     ZkBeta8 beta8;
     for (int k = 0; k < 5; ++k) beta8.t[k] = make_tab((uint32_t*)beta_mem + (uint64_t)k * 8 * D, D);
+    SplitEq sp0 = {}, sp1 = {};   // as built (H scaled after the weights are drawn); H with v0 bound
+    SplitConvArgs sca = {};
+    sp0.lb = sp1.lb = lb;
+    if (split) {
+        uint32_t* q = (uint32_t*)beta_mem;
+        for (int k = 0; k < 5; ++k) {
+            sca.src[k] = make_tab(q, nh);
+            sca.n[k] = nh;
+            q += 8 * nh;
+        }
+        for (int k = 0; k < 5; ++k) {
+            sca.src[5 + k] = make_tab(q, nl);
+            sca.n[5 + k] = nl;
+            q += 8 * nl;
+        }
+        for (int k = 0; k < 5; ++k) {
+            sp0.H[k].p = q;
+            sp0.H[k].ps = nh;
+            q += 9 * nh;
+            sca.dst[k] = sp0.H[k];
+        }
+        for (int k = 0; k < 5; ++k) {
+            sp1.H[k].p = q;
+            sp1.H[k].ps = (nh + 1) / 2;
+            q += 9 * ((nh + 1) / 2);
+        }
+        for (int k = 0; k < 5; ++k) {
+            sp0.L[k].p = q;
+            sp0.L[k].ps = nl;
+            q += 9 * nl;
+            sp1.L[k] = sp0.L[k];
+            sca.dst[5 + k] = sp0.L[k];
+        }
+    }
 
     // beta_J as an array of structures: one plane of J elements read through FrTab, then copied
     void* bj_tmp = zk_alloc(ctx, 64 * 32);
     int rc = bj_tmp ? ZKDL_OK : ZKDL_ENOMEM;
     FrTab bj_soa = make_tab(bj_tmp, J);
     if (rc == ZKDL_OK) {
-        BetaJob jobs[6];
+        BetaJob jobs[11];
         int nj = 0;
-        jobs[nj++] = BetaJob{st->chal + c_uz, li, beta8.t[0]};
-        jobs[nj++] = BetaJob{st->chal + c_ua, li, beta8.t[1]};
-        if (has_ga) {
-            jobs[nj++] = BetaJob{st->chal + c_uga, li, beta8.t[2]};
-            jobs[nj++] = BetaJob{st->chal + c_ugz, li, beta8.t[3]};
+        const int cpt[5] = {c_uz, c_ua, c_uga, c_ugz, c_ubin};
+        for (int k = 0; k < 5; ++k) {
+            if ((k == 2 || k == 3) && !has_ga) continue;
+            if (split) {
+                jobs[nj++] = BetaJob{st->chal + cpt[k], hb, sca.src[k]};
+                jobs[nj++] = BetaJob{st->chal + cpt[k] + hb, lb, sca.src[5 + k]};
+            } else {
+                jobs[nj++] = BetaJob{st->chal + cpt[k], li, beta8.t[k]};
+            }
         }
-        jobs[nj++] = BetaJob{st->chal + c_ubin, li, beta8.t[4]};
         jobs[nj++] = BetaJob{st->chal + c_ubin + li, lj, bj_soa};
         rc = zk_build_beta_many(ctx, jobs, nj);
     }
@@ -1766,6 +1888,11 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         return rc;
     }
     zk_launch_soa_to_aos(ctx, bj_soa, J, bJ);
+    if (split) {
+        if (!has_ga)   // tables that are not built are not converted either
+            for (int k = 2; k <= 3; ++k) sca.n[k] = sca.n[5 + k] = 0;
+        hipLaunchKernelGGL(k_zk_split_convert, dim3(blocks_for(nh > nl ? nh : nl, 64), 10), dim3(ZK_BLOCK), 0, ctx->stream, sca);
+    }
 
     PrepArgs pa;
     pa.z = z_dev;
@@ -1775,10 +1902,9 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     pa.r_bits = R;
     pa.beta = beta8;
     pa.tabs = tabs;
-    // the first two i-rounds of the linear equations read the integers (they must exist, and
-    // the line values must fit 58 bits)
-    const int lin_from_ints = li >= 2 && nbits <= 56;
+    const int lin_from_ints = split;
     pa.write_vals = !lin_from_ints;
+    pa.sp = sp0;
     pa.part = ctx->partials;
     pa.st = st;
     unsigned nb = blocks_for(D, ZK_MAX_PART_BLOCKS);
@@ -1792,8 +1918,12 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     ca.claim0_off = claim0_off;
     ca.chal_r = c_r;
     hipLaunchKernelGGL(k_zk_claims, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ca);
-    hipLaunchKernelGGL(k_zk_scale, dim3(blocks_for(D, 65536)), dim3(ZK_BLOCK), 0, ctx->stream, beta8, tabs, D,
-                       (const Fr*)st->weights, has_ga);
+    if (split)
+        hipLaunchKernelGGL(k_zk_split_scale, dim3(blocks_for(nh, 64), 4), dim3(ZK_BLOCK), 0, ctx->stream, sp0, nh,
+                           (const Fr*)st->weights, has_ga);
+    else
+        hipLaunchKernelGGL(k_zk_scale, dim3(blocks_for(D, 65536)), dim3(ZK_BLOCK), 0, ctx->stream, beta8, tabs, D,
+                           (const Fr*)st->weights, has_ga);
 
     BinArgs ba;
     ba.z = z_dev;
@@ -1812,6 +1942,10 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     ba.chal = nullptr;
     ba.m = 0;
     ba.part = nullptr;
+    ba.split = 0;
+    ba.sH = sp0.H[4];
+    ba.sL = sp0.L[4];
+    ba.s_lb = lb;
 
     for (int t = 0; t < li; ++t) {
         const uint64_t m = D >> (t + 1);
@@ -1826,6 +1960,9 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         ra.lin.ga = ga_dev;
         ra.lin.nbits = nbits;
         ra.lin.r_bits = R;
+        ra.lin.sp = t == 0 ? sp0 : sp1;
+        ba.split = split && t <= 1;
+        ba.sH = t == 0 ? sp0.H[4] : sp1.H[4];
         // few pairs: 16 per block, spread over (table, pair) and (point, equation, pair) threads
         ra.lin_small = !ra.lin.from_ints && m <= (uint64_t)LIN_SMALL_PAIRS * (ZK_MAX_PART_BLOCKS / 2);
         const unsigned nb_lin = ra.lin_small ? (unsigned)((m + LIN_SMALL_PAIRS - 1) / LIN_SMALL_PAIRS)
@@ -1875,6 +2012,9 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         zk_prof_end(ctx);
         // g(1) is taken from the running claim: the binarity kernels leave it out
         zk_launch_finalise(ctx, (int)(nb_lin + nb_bin), 4, c_v + t, rounds_off + (uint32_t)t * 128, 0, 0, 1);
+        if (split && t == 0)   // round 1 reads the H factors with v0 bound
+            hipLaunchKernelGGL(k_zk_split_fold, dim3(blocks_for(nh / 2, 64), 5), dim3(ZK_BLOCK), 0, ctx->stream, sp0, sp1,
+                               nh / 2, (const Fr*)&st->chal[c_v], has_ga);
         if (t + 1 == mat_bound) {
             // bind the first challenges: bits -> field elements, one look-up per entry
             int jc = nbits;
