@@ -241,6 +241,7 @@ struct LinArgs {
     const int64_t* ga;
     int nbits, r_bits;
     SplitEq sp;            // with from_ints: the equality tables in two factors (H bound as far as the round needs)
+    unsigned eq_blocks;    // round 0 with from_ints: blocks per equation (block / eq_blocks = equation)
 };
 
 // pair (lo, hi) of a lazy table, folded with the previous challenge first when FOLD; both
@@ -403,89 +404,128 @@ __device__ __forceinline__ F9 cols11_value(const uint64_t* cols) {
 
 // The four input claims from the integers (same bounds as round 0 below): dot products of the
 // equality tables as built with Z, (1 - sign) Z', G_A, (1 - sign) G_A'; also the range check.
+// sum_i H[ih] L[il] c_i = sum_ih H[ih] (sum_il L[il] c_i): a block takes a contiguous range of i and a
+// thread keeps the inner sums (9 x 2 limb products, no reduction) for as long as its ih stays the
+// same; when it changes the sums are reduced and multiplied by H[ih].
 __global__ __launch_bounds__(ZK_BLOCK) void k_zk_prepare_int(PrepArgs a) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     uint64_t cols[4][11];
+    F9 acc[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < 4; ++q) {
+        acc[q] = f9_zero();
 #pragma unroll
         for (int c = 0; c < 11; ++c) cols[q][c] = 0;
+    }
     bool bad = false;
-    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < a.D;
-         i += (uint64_t)gridDim.x * blockDim.x) {
+    const int lb = a.sp.lb;
+    const uint64_t per = ((a.D + gridDim.x - 1) / gridDim.x + ZK_BLOCK - 1) / ZK_BLOCK * ZK_BLOCK;
+    const uint64_t i0 = blockIdx.x * per, i1 = i0 + per < a.D ? i0 + per : a.D;
+    const uint64_t none = ~(uint64_t)0;
+    uint64_t cur = none;
+    auto flush = [&](uint64_t ih) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (q >= 2 && !a.ga) continue;
+            acc[q] = f9_norm_reduce(f9_add(acc[q], f9_mul(f9tab_ld(a.sp.H[q], ih), cols11_value(cols[q]))));
+#pragma unroll
+            for (int c = 0; c < 11; ++c) cols[q][c] = 0;
+        }
+    };
+    for (uint64_t i = i0 + threadIdx.x; i < i1; i += ZK_BLOCK) {
+        const uint64_t ih = i >> lb, il = i & (((uint64_t)1 << lb) - 1);
+        if (ih != cur) {
+            if (cur != none) flush(cur);
+            cur = ih;
+        }
         const int64_t z = a.z[i];
         bad |= !in_range(z, a.nbits);
         const IntRow rz = int_row(z, a.nbits, a.r_bits);
-        cols11_mac_signed(cols[0], split_entry(a.sp.H[0], a.sp.L[0], a.sp.lb, i), rz.z);
-        cols11_mac_signed(cols[1], split_entry(a.sp.H[1], a.sp.L[1], a.sp.lb, i), rz.ns * rz.zp);
+        cols11_mac_signed(cols[0], f9tab_ld(a.sp.L[0], il), rz.z);
+        cols11_mac_signed(cols[1], f9tab_ld(a.sp.L[1], il), rz.ns * rz.zp);
         cols11_carry(cols[0]);
         cols11_carry(cols[1]);
         if (a.ga) {
             const int64_t g = a.ga[i];
             bad |= !in_range(g, a.nbits);
-            cols11_mac_signed(cols[2], split_entry(a.sp.H[2], a.sp.L[2], a.sp.lb, i), g);
-            cols11_mac_signed(cols[3], split_entry(a.sp.H[3], a.sp.L[3], a.sp.lb, i), rz.ns * rescale_half_up(g, a.r_bits));
+            cols11_mac_signed(cols[2], f9tab_ld(a.sp.L[2], il), g);
+            cols11_mac_signed(cols[3], f9tab_ld(a.sp.L[3], il), rz.ns * rescale_half_up(g, a.r_bits));
             cols11_carry(cols[2]);
             cols11_carry(cols[3]);
         }
     }
+    if (cur != none) flush(cur);
     if (bad) atomicOr(&a.st->err, 1u);
-    F9 acc[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] = cols11_value(cols[q]);
     const Fr s = block_sum_lazy<4>(acc, red);
     if (threadIdx.x < 4) a.part[(uint64_t)blockIdx.x * 4 + threadIdx.x] = s;
 }
 
 // Round 0.  Bounds: |Z| < 2^55, so a line value |3 hi - 2 lo| < 2^57.4; |Z'| <= 2^54, the line of
 // 1 - sign is within [-2, 3]: their product is below 2^58.
-__device__ __forceinline__ void lin0_int_body(const LinArgs& a, const unsigned bx, const unsigned gx) {
+// The pair (b, b + m) differs in the leading variable, which lies in H: with b = (bh, bl),
+//   sum_b beta(x, b) c_b(x) = sum_bh Hline_bh(x) (sum_bl L[bl] c_b(x)),
+// so a block takes one equation and a contiguous range of b, a thread keeps the inner sums for
+// as long as its bh stays the same, and only then reduces them and multiplies by the line of H.
+__device__ __forceinline__ void lin0_int_body(const LinArgs& a, const unsigned bx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    const unsigned nbq = a.eq_blocks, e = bx / nbq, q = bx % nbq;
+    const uint64_t m = a.m;
+    const int lb = a.sp.lb;
+    const uint64_t hh = m >> lb;                  // H entries per half
+    const uint64_t per = ((m + nbq - 1) / nbq + ZK_BLOCK - 1) / ZK_BLOCK * ZK_BLOCK;
+    const uint64_t b0 = q * per, b1 = b0 + per < m ? b0 + per : m;
+    const F9Tab H = a.sp.H[e], L = a.sp.L[e];
     uint64_t cols[3][11];
+    F9 tot[3];
 #pragma unroll
-    for (int x = 0; x < 3; ++x)
+    for (int x = 0; x < 3; ++x) {
+        tot[x] = f9_zero();
 #pragma unroll
         for (int c = 0; c < 11; ++c) cols[x][c] = 0;
-    const uint64_t m = a.m;
-    for (uint64_t b = bx * (uint64_t)blockDim.x + threadIdx.x; b < m; b += (uint64_t)gx * blockDim.x) {
-        const IntRow zl = int_row(a.z[b], a.nbits, a.r_bits), zh = int_row(a.z[b + m], a.nbits, a.r_bits);
-        int64_t nsq[3];
-        F9 lo, hi, p[3];
-#pragma unroll
-        for (int x = 0; x < 3; ++x) nsq[x] = zl.ns + (x ? x + 1 : 0) * (zh.ns - zl.ns);
-        lo = split_entry(a.sp.H[0], a.sp.L[0], a.sp.lb, b);
-        hi = split_entry(a.sp.H[0], a.sp.L[0], a.sp.lb, b + m);
-        line3_reduced(lo, hi, p);
-#pragma unroll
-        for (int x = 0; x < 3; ++x) cols11_mac_signed(cols[x], p[x], zl.z + (x ? x + 1 : 0) * (zh.z - zl.z));
-        lo = split_entry(a.sp.H[1], a.sp.L[1], a.sp.lb, b);
-        hi = split_entry(a.sp.H[1], a.sp.L[1], a.sp.lb, b + m);
-        line3_reduced(lo, hi, p);
-#pragma unroll
-        for (int x = 0; x < 3; ++x)
-            cols11_mac_signed(cols[x], p[x], nsq[x] * (zl.zp + (x ? x + 1 : 0) * (zh.zp - zl.zp)));
-        if (a.has_ga) {
-            const IntRow gl = int_row(a.ga[b], a.nbits, a.r_bits), gh = int_row(a.ga[b + m], a.nbits, a.r_bits);
-            lo = split_entry(a.sp.H[2], a.sp.L[2], a.sp.lb, b);
-            hi = split_entry(a.sp.H[2], a.sp.L[2], a.sp.lb, b + m);
-            line3_reduced(lo, hi, p);
-#pragma unroll
-            for (int x = 0; x < 3; ++x) cols11_mac_signed(cols[x], p[x], gl.z + (x ? x + 1 : 0) * (gh.z - gl.z));
-            lo = split_entry(a.sp.H[3], a.sp.L[3], a.sp.lb, b);
-            hi = split_entry(a.sp.H[3], a.sp.L[3], a.sp.lb, b + m);
-            line3_reduced(lo, hi, p);
-#pragma unroll
-            for (int x = 0; x < 3; ++x)
-                cols11_mac_signed(cols[x], p[x], nsq[x] * (gl.zp + (x ? x + 1 : 0) * (gh.zp - gl.zp)));
-        }
-        // four terms of two products below 2^59.6 per column, then the carries
-#pragma unroll
-        for (int x = 0; x < 3; ++x) cols11_carry(cols[x]);
     }
-    F9 acc[3];
+    const uint64_t none = ~(uint64_t)0;
+    uint64_t cur = none;
+    auto flush = [&](uint64_t bh) {
+        F9 hl[3];
+        line3_reduced(f9tab_ld(H, bh), f9tab_ld(H, bh + hh), hl);
 #pragma unroll
-    for (int x = 0; x < 3; ++x) acc[x] = cols11_value(cols[x]);
-    const Fr s = block_sum_lazy<3>(acc, red);
+        for (int x = 0; x < 3; ++x) {
+            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(hl[x], cols11_value(cols[x]))));
+#pragma unroll
+            for (int c = 0; c < 11; ++c) cols[x][c] = 0;
+        }
+    };
+    for (uint64_t b = b0 + threadIdx.x; b < b1; b += ZK_BLOCK) {
+        const uint64_t bh = b >> lb;
+        if (bh != cur) {
+            if (cur != none) flush(cur);
+            cur = bh;
+        }
+        const IntRow zl = int_row(a.z[b], a.nbits, a.r_bits), zh = int_row(a.z[b + m], a.nbits, a.r_bits);
+        int64_t vl, vh;   // the value whose line is taken, before the factor 1 - sign
+        if (e == 0) {
+            vl = zl.z;
+            vh = zh.z;
+        } else if (e == 1) {
+            vl = zl.zp;
+            vh = zh.zp;
+        } else {
+            const int64_t gl = a.ga[b], gh = a.ga[b + m];
+            vl = e == 2 ? gl : rescale_half_up(gl, a.r_bits);
+            vh = e == 2 ? gh : rescale_half_up(gh, a.r_bits);
+        }
+        const F9 lv = f9tab_ld(L, b & (((uint64_t)1 << lb) - 1));
+#pragma unroll
+        for (int x = 0; x < 3; ++x) {
+            const int64_t xx = x ? x + 1 : 0;
+            int64_t c = vl + xx * (vh - vl);
+            if (e & 1) c *= zl.ns + xx * (zh.ns - zl.ns);
+            cols11_mac_signed(cols[x], lv, c);
+            cols11_carry(cols[x]);
+        }
+    }
+    if (cur != none) flush(cur);
+    const Fr s = block_sum_lazy<3>(tot, red);
     Fr* pp = a.part + (uint64_t)bx * 4;
     if (threadIdx.x < 3) pp[threadIdx.x ? threadIdx.x + 1 : 0] = s;
     else if (threadIdx.x == 3) pp[1] = fr_zero();
@@ -730,6 +770,46 @@ __device__ __forceinline__ F9 masked_sum9(const F9* sbj, uint64_t mask) {
     return f9_norm(s);
 }
 
+// Sums of beta_J over column sets by table: the columns are cut into groups of BJ_BITS and
+// tab[g][e] holds the sum of beta_J(BJ_BITS g + i) over the set bits i of e (normal, below
+// BJ_BITS r), so a masked sum is one table entry per group and the same work for every lane.
+constexpr int BJ_BITS = 7;
+constexpr int BJ_MAXG = (64 + BJ_BITS - 1) / BJ_BITS;
+constexpr int BJ_TAB_WORDS = BJ_MAXG * (1 << BJ_BITS) * 9;
+
+// sbj: beta_J as lazy limbs (64 entries, zero beyond nbits); all threads of the block
+__device__ __forceinline__ void bj_tables_build(uint32_t* tab, const F9* sbj, int groups) {
+    for (int idx = threadIdx.x; idx < groups << BJ_BITS; idx += blockDim.x) {
+        const int g = idx >> BJ_BITS, e = idx & ((1 << BJ_BITS) - 1);
+        F9 s = f9_zero();
+#pragma unroll
+        for (int i = 0; i < BJ_BITS; ++i)
+            if (((e >> i) & 1) && BJ_BITS * g + i < 64) s = f9_add(s, sbj[BJ_BITS * g + i]);
+        s = f9_norm(s);
+#pragma unroll
+        for (int l = 0; l < 9; ++l) tab[idx * 9 + l] = s.v[l];
+    }
+}
+
+// sum of beta_J over the set bits of mask: normal, below 64 r
+__device__ __forceinline__ F9 bj_masked_sum(const uint32_t* tab, uint64_t mask, int groups) {
+    F9 s = f9_zero();
+#pragma unroll
+    for (int g = 0; g < BJ_MAXG; ++g) {
+        if (g < groups) {
+            const uint32_t* e = tab + ((g << BJ_BITS) + (uint32_t)((mask >> (BJ_BITS * g)) & ((1u << BJ_BITS) - 1))) * 9;
+#pragma unroll
+            for (int l = 0; l < 9; ++l) s.v[l] += e[l];
+        }
+        if (g == 6) s = f9_norm(s);   // seven entries with limbs below 2^29 each so far
+    }
+    s = f9_norm(s);
+    // keep the scheduler from starting the next sum's loads before this one is consumed: with
+    // several sums in flight the registers run out
+    __builtin_amdgcn_sched_barrier(0);
+    return s;
+}
+
 // Round 0: both halves are bits, a(x)^2 - a(x) = (x^2 - x) [lo != hi]; contributes
 // 2 beta_I(2, i') C(i') at x = 2 and 6 beta_I(3, i') C(i') at x = 3,
 // C = sum_j beta_J(j) ([z bits differ] + r' [g bits differ]).
@@ -749,26 +829,59 @@ __device__ __forceinline__ void bin0_body(const BinArgs& a, const unsigned bx, c
     acc[1] = f9_zero();
     const uint64_t m = a.m;
     const uint64_t keep = a.nbits >= 64 ? ~(uint64_t)0 : (((uint64_t)1 << a.nbits) - 1);
-    for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
-        const uint64_t dz = ((uint64_t)a.z[b] ^ (uint64_t)a.z[b + m]) & keep;
-        F9 c = masked_sum9(sbj[0], dz);                      // normal, below 64 r
-        if (a.has_ga) {
-            const uint64_t dg = ((uint64_t)a.ga[b] ^ (uint64_t)a.ga[b + m]) & keep;
-            c = f9_add(c, masked_sum9(sbj[1], dg));          // limbs below 2^30
+    if (a.split) {
+        // beta_I(x, b) = Hline_bh(x) L[bl]: a block takes a contiguous range of b and a thread adds up
+        // L[bl] C(b) for as long as its bh stays the same, then multiplies by the line of H
+        __shared__ uint32_t bjt[BJ_TAB_WORDS];   // masked sums of beta_J by table; slice 1 takes r' afterwards
+        const int groups = (a.nbits + BJ_BITS - 1) / BJ_BITS;
+        bj_tables_build(bjt, sbj[0], groups);
+        __syncthreads();
+        const F9 rp9 = fr_unpack(*a.rp);
+        const int lb = a.s_lb;
+        const uint64_t hh = m >> lb;
+        const uint64_t per = ((m + gx - 1) / gx + ZK_BLOCK - 1) / ZK_BLOCK * ZK_BLOCK;
+        const uint64_t b0 = bx * per, b1 = b0 + per < m ? b0 + per : m;
+        const uint64_t none = ~(uint64_t)0;
+        uint64_t cur = none;
+        F9 u = f9_zero();
+        auto flush = [&](uint64_t bh) {
+            const F9 lo = f9tab_ld(a.sH, bh), hi = f9tab_ld(a.sH, bh + hh);
+            const F9 dn = f9_norm(f9_sub(hi, lo));
+            const F9 b2 = f9_norm(f9_add(hi, dn)), b3 = f9_norm(f9_add(b2, dn));
+            acc[0] = f9_norm_reduce(f9_add(acc[0], f9_mul(b2, u)));
+            acc[1] = f9_norm_reduce(f9_add(acc[1], f9_mul(b3, u)));
+            u = f9_zero();
+        };
+        for (uint64_t b = b0 + tid; b < b1; b += ZK_BLOCK) {
+            const uint64_t bh = b >> lb;
+            if (bh != cur) {
+                if (cur != none) flush(cur);
+                cur = bh;
+            }
+            const uint64_t dz = ((uint64_t)a.z[b] ^ (uint64_t)a.z[b + m]) & keep;
+            F9 c = bj_masked_sum(bjt, dz, groups);               // normal, below 64 r
+            if (a.has_ga) {
+                const uint64_t dg = ((uint64_t)a.ga[b] ^ (uint64_t)a.ga[b + m]) & keep;
+                c = f9_add(c, f9_mul(rp9, bj_masked_sum(bjt, dg, groups)));   // limbs below 2^30
+            }
+            u = f9_norm_reduce(f9_add(u, f9_mul(f9tab_ld(a.sL, b & (((uint64_t)1 << lb) - 1)), c)));
         }
-        // round 0: the table is as built, fully reduced; line at x = 2, 3, normal
-        F9 lo, hi;
-        if (a.split) {
-            lo = split_entry(a.sH, a.sL, a.s_lb, b);
-            hi = split_entry(a.sH, a.sL, a.s_lb, b + m);
-        } else {
-            lo = f9tab_ld(a.bI, b);
-            hi = f9tab_ld(a.bI, b + m);
+        if (cur != none) flush(cur);
+    } else {
+        for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
+            const uint64_t dz = ((uint64_t)a.z[b] ^ (uint64_t)a.z[b + m]) & keep;
+            F9 c = masked_sum9(sbj[0], dz);                      // normal, below 64 r
+            if (a.has_ga) {
+                const uint64_t dg = ((uint64_t)a.ga[b] ^ (uint64_t)a.ga[b + m]) & keep;
+                c = f9_add(c, masked_sum9(sbj[1], dg));          // limbs below 2^30
+            }
+            // round 0: the table is as built, fully reduced; line at x = 2, 3, normal
+            const F9 lo = f9tab_ld(a.bI, b), hi = f9tab_ld(a.bI, b + m);
+            const F9 dn = f9_norm(f9_sub(hi, lo));
+            const F9 b2 = f9_norm(f9_add(hi, dn)), b3 = f9_norm(f9_add(b2, dn));
+            acc[0] = f9_norm_reduce(f9_add(acc[0], f9_mul(b2, c)));
+            acc[1] = f9_norm_reduce(f9_add(acc[1], f9_mul(b3, c)));
         }
-        const F9 dn = f9_norm(f9_sub(hi, lo));
-        const F9 b2 = f9_norm(f9_add(hi, dn)), b3 = f9_norm(f9_add(b2, dn));
-        acc[0] = f9_norm_reduce(f9_add(acc[0], f9_mul(b2, c)));
-        acc[1] = f9_norm_reduce(f9_add(acc[1], f9_mul(b3, c)));
     }
     // (x^2 - x) = 2 at x = 2 and 6 at x = 3
     acc[0] = f9_norm_reduce(f9_add(acc[0], acc[0]));
@@ -822,46 +935,6 @@ __device__ __forceinline__ void beta_line_fold(const BinArgs& a, uint64_t b, uin
     e[0] = lo;
     e[1] = f9_norm(f9_add(hi, dn));
     e[2] = f9_norm(f9_add(e[1], dn));
-}
-
-// Sums of beta_J over column sets by table: the columns are cut into groups of BJ_BITS and
-// tab[g][e] holds the sum of beta_J(BJ_BITS g + i) over the set bits i of e (normal, below
-// BJ_BITS r), so a masked sum is one table entry per group and the same work for every lane.
-constexpr int BJ_BITS = 7;
-constexpr int BJ_MAXG = (64 + BJ_BITS - 1) / BJ_BITS;
-constexpr int BJ_TAB_WORDS = BJ_MAXG * (1 << BJ_BITS) * 9;
-
-// sbj: beta_J as lazy limbs (64 entries, zero beyond nbits); all threads of the block
-__device__ __forceinline__ void bj_tables_build(uint32_t* tab, const F9* sbj, int groups) {
-    for (int idx = threadIdx.x; idx < groups << BJ_BITS; idx += blockDim.x) {
-        const int g = idx >> BJ_BITS, e = idx & ((1 << BJ_BITS) - 1);
-        F9 s = f9_zero();
-#pragma unroll
-        for (int i = 0; i < BJ_BITS; ++i)
-            if (((e >> i) & 1) && BJ_BITS * g + i < 64) s = f9_add(s, sbj[BJ_BITS * g + i]);
-        s = f9_norm(s);
-#pragma unroll
-        for (int l = 0; l < 9; ++l) tab[idx * 9 + l] = s.v[l];
-    }
-}
-
-// sum of beta_J over the set bits of mask: normal, below 64 r
-__device__ __forceinline__ F9 bj_masked_sum(const uint32_t* tab, uint64_t mask, int groups) {
-    F9 s = f9_zero();
-#pragma unroll
-    for (int g = 0; g < BJ_MAXG; ++g) {
-        if (g < groups) {
-            const uint32_t* e = tab + ((g << BJ_BITS) + (uint32_t)((mask >> (BJ_BITS * g)) & ((1u << BJ_BITS) - 1))) * 9;
-#pragma unroll
-            for (int l = 0; l < 9; ++l) s.v[l] += e[l];
-        }
-        if (g == 6) s = f9_norm(s);   // seven entries with limbs below 2^29 each so far
-    }
-    s = f9_norm(s);
-    // keep the scheduler from starting the next sum's loads before this one is consumed: with
-    // several sums in flight the registers run out
-    __builtin_amdgcn_sched_barrier(0);
-    return s;
 }
 
 // Round 1 on the integers.  m = D/4 quadruples of rows (i'', i''+m | i''+2m, i''+3m) = (x0, x1) in
@@ -1441,7 +1514,7 @@ template <int MODE>
 __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     if (blockIdx.x < a.nb_lin) {
         if (MODE <= 1 && a.lin.from_ints) {
-            if (MODE == 0) lin0_int_body(a.lin, blockIdx.x, a.nb_lin);
+            if (MODE == 0) lin0_int_body(a.lin, blockIdx.x);
             else lin1_int_body(a.lin, blockIdx.x, a.nb_lin);
         } else if (a.lin_small) lin_body_small<MODE != 0>(a.lin, blockIdx.x);
         else lin_body<MODE != 0>(a.lin, blockIdx.x, a.nb_lin);
@@ -1965,8 +2038,11 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         ba.sH = t == 0 ? sp0.H[4] : sp1.H[4];
         // few pairs: 16 per block, spread over (table, pair) and (point, equation, pair) threads
         ra.lin_small = !ra.lin.from_ints && m <= (uint64_t)LIN_SMALL_PAIRS * (ZK_MAX_PART_BLOCKS / 2);
-        const unsigned nb_lin = ra.lin_small ? (unsigned)((m + LIN_SMALL_PAIRS - 1) / LIN_SMALL_PAIRS)
-                                             : blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
+        const unsigned n_eq = has_ga ? 4 : 2;
+        ra.lin.eq_blocks = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / n_eq);
+        const unsigned nb_lin = ra.lin.from_ints && t == 0 ? n_eq * ra.lin.eq_blocks
+                                : ra.lin_small       ? (unsigned)((m + LIN_SMALL_PAIRS - 1) / LIN_SMALL_PAIRS)
+                                                     : blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
         ra.nb_lin = nb_lin;
         // beta_I: round 0 reads the table as built; round t >= 1 reads what round t-1 left (the
         // table as built for t = 1), binds v_{t-1} and leaves the folded pair in the other buffer
