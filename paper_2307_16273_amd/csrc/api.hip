@@ -132,6 +132,7 @@ extern "C" int zkdl_ctx_create(zkdl_ctx** out, int device, void* hip_stream) {
     ctx->n_chal = 0;
     ctx->proof_len = 0;
     ctx->prof_on = false;
+    ctx->zk_fill_threads = 131072;   // two waves on each of the 1024 SIMDs
     ctx->prof_used = 0;
     for (int i = 0; i < ZKDL_PROF_CLASSES; ++i) {
         ctx->prof_ms[i] = ctx->prof_bytes[i] = 0.0;
@@ -188,6 +189,12 @@ extern "C" int zkdl_ctx_destroy(zkdl_ctx* ctx) {
 }
 
 extern "C" int zkdl_last_hip_error(const zkdl_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+extern "C" int zkdl_ctx_set_fill_threads(zkdl_ctx* ctx, uint64_t threads) {
+    if (!ctx || threads < 1 || threads > ((uint64_t)1 << 24)) return ZKDL_EINVAL;
+    ctx->zk_fill_threads = threads;
+    return ZKDL_OK;
+}
 
 // ---------------------------------------------------------------------------
 // per-kernel timing

@@ -744,6 +744,13 @@ struct BinArgs {
     int split;             // rounds 0, 1: beta_I(i) = sH[i >> s_lb] sL[i & (2^s_lb - 1)] (sH bound as far as needed)
     F9Tab sH, sL;
     int s_lb;
+    // per pair index the sums over the columns SA = sum beta_J p(lo), SC = sum beta_J p(hi),
+    // SD = sum beta_J (hi - lo)^2, p(a) = a^2 - a, handed from one round to the next
+    // (entry (chunk, b) at index chunk * pairs + b; the chunks of a pair index add up)
+    F9Tab ps_in[3];        // what the previous round left (binp_body)
+    int ps_in_chunks;
+    F9Tab ps_out[3];       // written if ps_write
+    int ps_write;
     Fr* part;              // partials of this kernel
 };
 
@@ -1325,6 +1332,12 @@ __device__ __forceinline__ void bin3_body(const BinArgs& a, const unsigned bx, c
         // below, at most eight such limbs are added between carry passes, and what is
         // subtracted is below 2.6 r after f9_norm_reduce
         const F9 sa = f9_norm_reduce(f9_redc(cols[0])), sc = f9_redc(cols[1]), sd = f9_redc(cols[2]);
+        if (a.ps_write) {
+            const uint64_t at = (uint64_t)by * m + b;
+            f9tab_st(a.ps_out[0], at, sa);
+            f9tab_st(a.ps_out[1], at, f9_norm_reduce(sc));
+            f9tab_st(a.ps_out[2], at, f9_norm_reduce(sd));
+        }
         const F9 sc2 = f9_add(sc, sc), sd2 = f9_add(sd, sd);
         const F9 g2 = f9_norm(f9_sub(f9_add(sc2, sd2), sa));                             // -SA + 2 SC + 2 SD
         const F9 h3 = f9_norm(f9_add(f9_add(sc2, sc), f9_add(sd2, sd2)));                // 3 SC + 4 SD
@@ -1498,6 +1511,121 @@ __device__ __forceinline__ void binl_body(const BinArgs& a, const unsigned bx, c
     }
 }
 
+// The same rounds when the previous round left its column sums (SA, SC, SD) per pair index.
+// A pair of this round folds two pairs of the previous one (b and b + m of its 2m), and
+//   q_j(X) = (1 - X) p(lo_j) + X p(hi_j) - X (1 - X) (hi_j - lo_j)^2
+// summed over the columns at X = v (the challenge just bound) is what p of the folded entries
+// sums to: SA' = (1 - v) SA_b + v SC_b - v (1 - v) SD_b, SC' the same at b + m.  Only
+// SD' = sum_j beta_J (hi'_j - lo'_j)^2 needs the columns: one square per column instead of
+// three, one accumulator instead of three.  G(0) = SA', G(2) = -SA' + 2 SC' + 2 SD',
+// G(3) = -2 SA' + 3 SC' + 6 SD'.  With the columns cut into chunks, the thread of the first
+// chunk (and slice) takes SA' and SC', adding up the previous round's chunks.
+template <bool FOLD>
+__device__ __forceinline__ void binp_body(const BinArgs& a, const unsigned bx, const unsigned by, const unsigned gx) {
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    __shared__ F9 sbj[2][64];
+    const int tid = threadIdx.x;
+    if (tid < 128) {
+        const int j = tid & 63, k = tid >> 6;
+        F9 x = f9_zero();
+        if (j < a.nbits) x = fr_unpack(k == 0 ? a.bJ[j] : fr_mul(*a.rp, a.bJ[j]));
+        sbj[k][j] = x;
+    }
+    __syncthreads();
+    const uint64_t m = a.m;
+    const F9 v = fr_unpack(*a.vprev);     // the challenge that this round binds on the way
+    F9 u1, nvv;                           // 1 - v, v^2 - v
+    {
+        const Fr vf = *a.vprev;
+        u1 = fr_unpack(fr_sub(fr_one(), vf));
+        nvv = fr_unpack(fr_sub(fr_sqr(vf), vf));
+    }
+    const unsigned chunk = a.ksplit ? by >> 1 : by;
+    const int k0 = a.ksplit ? (int)(by & 1) : 0, k1 = a.ksplit ? k0 + 1 : (a.has_ga ? 2 : 1);
+    int j0 = chunk * a.jc, j1 = j0 + a.jc;
+    if (j1 > a.nbits) j1 = a.nbits;
+    F9 tot[3];
+#pragma unroll
+    for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
+    for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
+        uint64_t cols[17];
+#pragma unroll
+        for (int c = 0; c < 17; ++c) cols[c] = 0;
+        int pending = 0;
+        const int nk = k1 - k0, ncol = (j1 - j0) * nk;
+        ColRaw<FOLD> cur = col_load<FOLD>(a, k0, j0, b, m);
+        for (int c = 0; c < ncol; ++c) {
+            const int j = j0 + (nk == 2 ? c >> 1 : c), k = k0 + (nk == 2 ? (c & 1) : 0);
+            const int cn = c + 1 < ncol ? c + 1 : c;   // the last iteration asks for its own column again
+            const ColRaw<FOLD> nxt =
+                col_load<FOLD>(a, k0 + (nk == 2 ? (cn & 1) : 0), j0 + (nk == 2 ? cn >> 1 : cn), b, m);
+            F9 lo, hi;
+            if (FOLD) {
+                const F9Tab col = aux_col9(a, k, j);
+                lo = f9_norm_reduce(f9_add(cur.t[0], f9_mul(f9_sub(cur.t[2], cur.t[0]), v)));
+                hi = f9_norm_reduce(f9_add(cur.t[1], f9_mul(f9_sub(cur.t[3], cur.t[1]), v)));
+                f9tab_st(col, b, lo);
+                f9tab_st(col, b + m, hi);
+            } else {
+                lo = cur.t[0];
+                hi = cur.t[1];
+            }
+            const F9 d = f9_norm(f9_sub(hi, lo));     // normal, below 6.5 r
+            f9_cols_mac(cols, sbj[k][j], f9_mul(d, d));
+            if (++pending == 4) {
+                pending = 0;
+                f9_cols_norm<17>(cols);
+            }
+            cur = nxt;
+        }
+        f9_cols_norm<17>(cols);
+        const F9 sd = f9_norm_reduce(f9_redc(cols));   // at most 128 products below 2 r^2: below 4.8 r before
+        F9 sa = f9_zero(), sc = f9_zero();
+        if (chunk == 0 && k0 == 0) {
+            // the sums that the previous round left for its pairs b and b + m (2m pairs there)
+            F9 in[2][3];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int q = 0; q < 3; ++q) in[h][q] = f9_zero();
+            for (int c = 0; c < a.ps_in_chunks; ++c) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int q = 0; q < 3; ++q)
+                        in[h][q] = f9_norm_reduce(f9_add(in[h][q], f9tab_ld(a.ps_in[q], (uint64_t)c * 2 * m + b + h * m)));
+            }
+            // three products below 2.41 r^2 each: normal and below 2.41 r after the reducing pass
+            sa = f9_norm_reduce(f9_add(f9_add(f9_mul(u1, in[0][0]), f9_mul(v, in[0][1])), f9_mul(nvv, in[0][2])));
+            sc = f9_norm_reduce(f9_add(f9_add(f9_mul(u1, in[1][0]), f9_mul(v, in[1][1])), f9_mul(nvv, in[1][2])));
+        }
+        if (a.ps_write) {
+            const uint64_t at = (uint64_t)by * m + b;
+            f9tab_st(a.ps_out[0], at, sa);
+            f9tab_st(a.ps_out[1], at, sc);
+            f9tab_st(a.ps_out[2], at, sd);
+        }
+        F9 bi[3];
+        beta_line_fold(a, b, m, v, bi);
+        // limbs of sa, sc, sd are below 2^29: at most eight are added between carry passes; what is
+        // subtracted is below 2.6 r
+        const F9 sc2 = f9_add(sc, sc), sd2 = f9_add(sd, sd);
+        const F9 g2 = f9_norm(f9_sub(f9_add(sc2, sd2), sa));                             // -SA + 2 SC + 2 SD
+        const F9 h3 = f9_norm(f9_add(f9_add(sc2, sc), f9_add(sd2, sd2)));                // 3 SC + 4 SD
+        const F9 g3 = f9_norm(f9_sub(f9_sub(f9_add(h3, sd2), sa), sa));                  // ... + 2 SD - 2 SA
+        tot[0] = f9_norm_reduce(f9_add(tot[0], f9_mul(bi[0], sa)));
+        tot[1] = f9_norm_reduce(f9_add(tot[1], f9_mul(bi[1], g2)));
+        tot[2] = f9_norm_reduce(f9_add(tot[2], f9_mul(bi[2], g3)));
+    }
+    const uint64_t blk = (uint64_t)by * gx + bx;
+    {
+        const Fr s = block_sum_lazy<3>(tot, red);
+        Fr* p = a.part + blk * 4;
+        if (tid < 3) p[tid ? tid + 1 : 0] = s;
+        else if (tid == 3) p[1] = fr_zero();
+    }
+}
+
 // One launch per i-round: the first nb_lin blocks take the linear equations, the others the
 // binarity terms (column chunk = block / bin_gx).  The two parts share no table, so they run
 // side by side; their partial sums land in one array that the round's finaliser adds up.
@@ -1509,7 +1637,8 @@ struct ZkRoundArgs {
 };
 
 // MODE 0: first round; 1, 2, 5: rounds 1, 2, 3 on the integers; 3: first round on the columns
-// in memory; 4: later rounds (fold the columns with the previous challenge first)
+// in memory; 4: later rounds (fold the columns with the previous challenge first); 6, 7: as 3, 4
+// with the column sums of the previous round at hand
 template <int MODE>
 __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     if (blockIdx.x < a.nb_lin) {
@@ -1526,6 +1655,7 @@ __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     else if (MODE == 1) bin1_body(a.bin, bx, a.bin_gx);
     else if (MODE == 2) bin2_body(a.bin, bx, by, a.bin_gx);
     else if (MODE == 5) bin3_body(a.bin, bx, by, a.bin_gx);
+    else if (MODE >= 6) binp_body<MODE == 7>(a.bin, bx, by, a.bin_gx);
     else binl_body<MODE == 4>(a.bin, bx, by, a.bin_gx);
 }
 
@@ -1878,11 +2008,24 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     // split: packed H and L of the five points, then as lazy limbs H, H folded once, L
     const uint64_t split_words = 5 * (nh + nl) * 8 + 5 * (nh + (nh + 1) / 2 + nl) * 9;
     void* beta_mem = zk_alloc(ctx, split ? split_words * 4 : (uint64_t)5 * D * 32);
-    if (!mem || !beta_mem) {
+    // column sums handed from round to round (from round 3 on): two sets of three tables; a round
+    // with c chunks of m pairs leaves c m entries, and chunks appear only below the fill threshold
+    const uint64_t fill_threads = ctx->zk_fill_threads ? ctx->zk_fill_threads : 1;
+    constexpr unsigned PS_MAX_CHUNKS = 4;
+    const uint64_t ps_cap = li >= 4 ? ((D >> 4) > 4 * fill_threads ? (D >> 4) : 4 * fill_threads) : 0;
+    void* ps_mem = ps_cap ? zk_alloc(ctx, 6 * ps_cap * 36) : nullptr;
+    if (!mem || !beta_mem || (ps_cap && !ps_mem)) {
         zk_free(ctx, mem);
         zk_free(ctx, beta_mem);
+        zk_free(ctx, ps_mem);
         return ZKDL_ENOMEM;
     }
+    F9Tab ps_tab[2][3];
+    for (int q = 0; q < 6; ++q) {
+        ps_tab[q / 3][q % 3].p = (uint32_t*)ps_mem + (uint64_t)q * 9 * ps_cap;
+        ps_tab[q / 3][q % 3].ps = ps_cap;
+    }
+    int ps_prev_chunks = 0;   // != 0: the previous round left its column sums in ps_tab[(t - 1) & 1]
     uint32_t* base = (uint32_t*)mem;
     ZkTabs tabs;
     for (int k = 0; k < LIN_TABLES; ++k) {
@@ -1958,6 +2101,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         zk_free(ctx, bj_tmp);
         zk_free(ctx, mem);
         zk_free(ctx, beta_mem);
+        zk_free(ctx, ps_mem);
         return rc;
     }
     zk_launch_soa_to_aos(ctx, bj_soa, J, bJ);
@@ -2055,7 +2199,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         // Every (pair index, chunk) thread pays the beta_I fold and three reductions on top of its
         // columns, about as much as one column costs: split only until the machine is full
         // (two waves per SIMD: 2^17 threads).
-        constexpr uint64_t ZK_FILL_THREADS = 131072;
+        const uint64_t ZK_FILL_THREADS = fill_threads;
         int jc = nbits;
         if (t >= 2)
             while ((uint64_t)((nbits + jc - 1) / jc) * m < ZK_FILL_THREADS && jc > 1) jc = (jc + 1) / 2;
@@ -2067,6 +2211,18 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         const unsigned nb_bin = bx * chunks;
         ba.jc = jc;
         ba.chal = t == 0 ? nullptr : t < mat_bound ? &st->chal[c_v] : t > mat_bound ? &st->chal[c_v + t - 1] : nullptr;
+        // column sums: round 3 on the integers and the rounds on the columns that use them leave
+        // theirs for the next round, as long as the columns are cut into few chunks
+        const bool ps_ok = mat_bound == 4 && t >= 3 && chunks <= PS_MAX_CHUNKS && (uint64_t)chunks * m <= ps_cap;
+        const bool ps_use = ps_ok && t >= mat_bound && ps_prev_chunks != 0;
+        const bool ps_produce = ps_ok && (t == 3 || ps_use);
+        for (int q = 0; q < 3; ++q) {
+            ba.ps_in[q] = ps_tab[(t + 1) & 1][q];
+            ba.ps_out[q] = ps_tab[t & 1][q];
+        }
+        ba.ps_in_chunks = ps_prev_chunks;
+        ba.ps_write = ps_produce ? 1 : 0;
+        ps_prev_chunks = ps_produce ? (int)chunks : 0;
         ra.bin = ba;
         ra.bin_gx = bx;
         // algorithmic bytes: the linear tables (9 of them with G_A, 5 without) and beta_I in 36-byte
@@ -2083,7 +2239,9 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         else if (t == 1) launch_zk_round<1>(ctx, ra, nb_bin);
         else if (t == 2) launch_zk_round<2>(ctx, ra, nb_bin);
         else if (t < mat_bound) launch_zk_round<5>(ctx, ra, nb_bin);
+        else if (t == mat_bound && ps_use) launch_zk_round<6>(ctx, ra, nb_bin);
         else if (t == mat_bound) launch_zk_round<3>(ctx, ra, nb_bin);
+        else if (ps_use) launch_zk_round<7>(ctx, ra, nb_bin);
         else launch_zk_round<4>(ctx, ra, nb_bin);
         zk_prof_end(ctx);
         // g(1) is taken from the running claim: the binarity kernels leave it out
@@ -2129,5 +2287,6 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     zk_free(ctx, bj_tmp);
     zk_free(ctx, mem);
     zk_free(ctx, beta_mem);
+    zk_free(ctx, ps_mem);
     return ZKDL_OK;
 }

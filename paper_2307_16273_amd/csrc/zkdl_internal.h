@@ -69,6 +69,8 @@ struct zkdl_ctx {
     // kernel absorbs before anything else
     uint8_t pend[ZK_PEND_CAP];
     uint32_t pend_len;
+    // zkReLU: the columns of a round are cut into chunks until this many threads are busy
+    uint64_t zk_fill_threads;
     // optional per-kernel-class timing with HIP events on the context's stream
     bool prof_on;
     struct ProfSpan {

@@ -320,6 +320,29 @@ def test_zkrelu(lib, ctx, d_len, with_ga, q, r):
     assert tr.digest() == ots.digest()
 
 
+@pytest.mark.parametrize("fill,d_len,with_ga", [(1, 1024, True), (64, 1024, True), (128, 512, False), (4096, 2048, True)])
+def test_zkrelu_column_chunking(lib, fill, d_len, with_ga):
+    """The proof does not depend on how the bit columns are cut into chunks.  With a low fill
+    threshold the rounds on the columns run whole columns per thread (or a few chunks) and hand
+    their column sums from round to round, which the default threshold does only for large D."""
+    import paper_2307_16273_amd as zk
+    say(f"zkrelu fill_threads={fill} D={d_len} ga={with_ga}")
+    c2 = zk.Context(0)
+    c2.set_fill_threads(fill)
+    rng = np.random.default_rng(d_len + fill)
+    lim = 1 << 47
+    z = rng.integers(-lim, lim, d_len, dtype=np.int64)
+    ga = rng.integers(-lim, lim, d_len, dtype=np.int64) if with_ga else None
+    tr = lib.Transcript(23)
+    got = lib.zkrelu_prove(c2, z, ga, tr, 32, 16)
+    ots = OracleTranscript(23)
+    buf, info = P.zkrelu_prove(z.tolist(), ga.tolist() if with_ga else None, 32, 16, ots)
+    assert got["proof"] == buf
+    assert got["points"] == ots.challenges
+    assert tr.digest() == ots.digest()
+    c2.close()
+
+
 @pytest.mark.parametrize("q,r", [(40, 16), (32, 16), (55, 1)])
 def test_zkrelu_extreme_values(lib, ctx, q, r):
     """Every entry at an end of the (Q+R)-bit range, arranged so that the pairs and quadruples
