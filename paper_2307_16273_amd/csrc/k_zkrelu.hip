@@ -944,6 +944,60 @@ __device__ __forceinline__ void beta_line_fold(const BinArgs& a, uint64_t b, uin
     e[2] = f9_norm(f9_add(e[1], dn));
 }
 
+// Column sums from round to round.  With p(a) = a^2 - a the summand of a pair (lo, hi) is
+//   q(X) = (1 - X) p(lo) + X p(hi) - X (1 - X) (hi - lo)^2,
+// so the sums over the columns SA = sum beta_J p(lo), SC = sum beta_J p(hi), SD = sum beta_J (hi - lo)^2
+// give the round's G(0) = SA, G(2) = -SA + 2 SC + 2 SD, G(3) = -2 SA + 3 SC + 6 SD, and at X = v (the
+// challenge bound next) what p of the folded entries sums to.  A pair of the next round folds the
+// pairs b and b + m of this one, hence its SA' = (1 - v) SA_b + v SC_b - v (1 - v) SD_b and SC' the
+// same at b + m: only SD' needs the columns again.
+struct PsumConsts {
+    F9 u1, v, nvv;   // 1 - v, v, v^2 - v
+};
+__device__ __forceinline__ PsumConsts psum_consts(const Fr* vp) {
+    const Fr vf = *vp;
+    PsumConsts k;
+    k.u1 = fr_unpack(fr_sub(fr_one(), vf));
+    k.v = fr_unpack(vf);
+    k.nvv = fr_unpack(fr_sub(fr_sqr(vf), vf));
+    return k;
+}
+// SA', SC' of pair index b (of m) from what the previous round left (2m pairs, ps_in_chunks chunks
+// that add up); both normal and below 2.41 r
+__device__ __forceinline__ void psum_bind(const BinArgs& a, uint64_t b, uint64_t m, const PsumConsts& k, F9& sa, F9& sc) {
+    F9 in[2][3];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int q = 0; q < 3; ++q) in[h][q] = f9_zero();
+    for (int c = 0; c < a.ps_in_chunks; ++c) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int q = 0; q < 3; ++q)
+                in[h][q] = f9_norm_reduce(f9_add(in[h][q], f9tab_ld(a.ps_in[q], (uint64_t)c * 2 * m + b + h * m)));
+    }
+    // three products below 2.41 r^2 each
+    sa = f9_norm_reduce(f9_add(f9_add(f9_mul(k.u1, in[0][0]), f9_mul(k.v, in[0][1])), f9_mul(k.nvv, in[0][2])));
+    sc = f9_norm_reduce(f9_add(f9_add(f9_mul(k.u1, in[1][0]), f9_mul(k.v, in[1][1])), f9_mul(k.nvv, in[1][2])));
+}
+// the round's G(0), G(2), G(3) times the beta_I line, added to tot; sa below 2.6 r, all normal with
+// limbs below 2^29 (at most eight are added between carry passes)
+__device__ __forceinline__ void psum_accumulate(F9 tot[3], const F9 bi[3], const F9& sa, const F9& sc, const F9& sd) {
+    const F9 sc2 = f9_add(sc, sc), sd2 = f9_add(sd, sd);
+    const F9 g2 = f9_norm(f9_sub(f9_add(sc2, sd2), sa));                             // -SA + 2 SC + 2 SD
+    const F9 h3 = f9_norm(f9_add(f9_add(sc2, sc), f9_add(sd2, sd2)));                // 3 SC + 4 SD
+    const F9 g3 = f9_norm(f9_sub(f9_sub(f9_add(h3, sd2), sa), sa));                  // ... + 2 SD - 2 SA
+    tot[0] = f9_norm_reduce(f9_add(tot[0], f9_mul(bi[0], sa)));
+    tot[1] = f9_norm_reduce(f9_add(tot[1], f9_mul(bi[1], g2)));
+    tot[2] = f9_norm_reduce(f9_add(tot[2], f9_mul(bi[2], g3)));
+}
+__device__ __forceinline__ void psum_store(const BinArgs& a, uint64_t at, const F9& sa, const F9& sc, const F9& sd) {
+    f9tab_st(a.ps_out[0], at, sa);
+    f9tab_st(a.ps_out[1], at, sc);
+    f9tab_st(a.ps_out[2], at, sd);
+}
+
 // Round 1 on the integers.  m = D/4 quadruples of rows (i'', i''+m | i''+2m, i''+3m) = (x0, x1) in
 // {(0,0), (0,1), (1,0), (1,1)}; bit j of row (x0, x1) is B_{x0,x1}(j).  With x0 bound to v0 the
 // entry that the round interpolates is
@@ -1024,6 +1078,8 @@ __device__ __forceinline__ void bin1_body(const BinArgs& a, const unsigned bx, c
         beta_line_fold(a, b, m, vprev9, bi);
         // sums of at most 6 products below 128 r^2: the reduced values are normal and below 12 r
         const F9 ra = red3[0], rc = red3[1], rb = red3[2];
+        if (a.ps_write)
+            psum_store(a, b, f9_norm_reduce(ra), f9_norm_reduce(rc), f9_norm_reduce(f9_add(f9_add(rb, ra), rc)));
         // limbs of ra, rb, rc are below 2^29: at most eight of them are added between carry passes
         const F9 c2 = f9_add(rc, rc), c4 = f9_add(c2, c2), b2 = f9_add(rb, rb), a2 = f9_add(ra, ra);
         const F9 g2 = f9_norm(f9_add(f9_add(ra, c4), b2));                 // A' + 4 C' + 2 B
@@ -1099,6 +1155,7 @@ __device__ __forceinline__ void bound2_values(const Fr* chal, F9* val16) {
     }
 }
 
+template <bool PSUM>
 __device__ __forceinline__ void bin2_body(const BinArgs& a, const unsigned bx, const unsigned by, const unsigned gx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ F9 sbj[2][64];
@@ -1121,13 +1178,21 @@ __device__ __forceinline__ void bin2_body(const BinArgs& a, const unsigned bx, c
         e[0] = lo;
         e[1] = f9_norm(f9_add(hi, dn));
         e[2] = f9_norm(f9_add(e[1], dn));
+        if (PSUM) {   // only (hi - lo)^2 is needed, kept in the first table
+            const F9 q = f9_mul(dn, dn);
 #pragma unroll
-        for (int x = 0; x < 3; ++x) {
-            const F9 q = f9_mul(e[x], f9_sub(e[x], one9));
+            for (int l = 0; l < 9; ++l) qlut[0][l][tid] = q.v[l];
+        } else {
 #pragma unroll
-            for (int l = 0; l < 9; ++l) qlut[x][l][tid] = q.v[l];
+            for (int x = 0; x < 3; ++x) {
+                const F9 q = f9_mul(e[x], f9_sub(e[x], one9));
+#pragma unroll
+                for (int l = 0; l < 9; ++l) qlut[x][l][tid] = q.v[l];
+            }
         }
     }
+    PsumConsts pk;
+    if (PSUM) pk = psum_consts(a.vprev);
     __syncthreads();
     const uint64_t m = a.m;
     const F9 vprev9 = fr_unpack(*a.vprev);
@@ -1156,7 +1221,7 @@ __device__ __forceinline__ void bin2_body(const BinArgs& a, const unsigned bx, c
                 for (int s2 = 0; s2 < 8; ++s2) w[s2] >>= 1;
                 const F9 bj = sbj[k][j];
 #pragma unroll
-                for (int x = 0; x < 3; ++x) {
+                for (int x = 0; x < (PSUM ? 1 : 3); ++x) {
                     F9 q;
 #pragma unroll
                     for (int l = 0; l < 9; ++l) q.v[l] = qlut[x][l][C];
@@ -1165,16 +1230,25 @@ __device__ __forceinline__ void bin2_body(const BinArgs& a, const unsigned bx, c
                 if (++pending == 4) {
                     pending = 0;
 #pragma unroll
-                    for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
+                    for (int x = 0; x < (PSUM ? 1 : 3); ++x) f9_cols_norm<17>(cols[x]);
                 }
             }
         }
         F9 bi[3];
         beta_line_fold(a, b, m, vprev9, bi);
+        if (PSUM) {
+            f9_cols_norm<17>(cols[0]);
+            const F9 sd = f9_norm_reduce(f9_redc(cols[0]));
+            F9 sa = f9_zero(), sc = f9_zero();
+            if (chunk == 0 && k0 == 0) psum_bind(a, b, m, pk, sa, sc);
+            if (a.ps_write) psum_store(a, (uint64_t)by * m + b, sa, sc, sd);
+            psum_accumulate(tot, bi, sa, sc, sd);
+        } else {
 #pragma unroll
-        for (int x = 0; x < 3; ++x) {
-            f9_cols_norm<17>(cols[x]);
-            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_redc(cols[x]))));
+            for (int x = 0; x < 3; ++x) {
+                f9_cols_norm<17>(cols[x]);
+                tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(bi[x], f9_redc(cols[x]))));
+            }
         }
     }
     const uint64_t blk = (uint64_t)by * gx + bx;
@@ -1266,6 +1340,7 @@ __device__ __forceinline__ void pair_codes16(const uint64_t w[16], int j, uint32
     chi = pair_code8(o);
 }
 
+template <bool PSUM>
 __device__ __forceinline__ void bin3_body(const BinArgs& a, const unsigned bx, const unsigned by, const unsigned gx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ F9 sbj[2][64];
@@ -1280,7 +1355,9 @@ __device__ __forceinline__ void bin3_body(const BinArgs& a, const unsigned bx, c
         sbj[k][j] = x;
     }
     bound3_values(a.chal, val16, alut);
-    {
+    PsumConsts pk;
+    if (PSUM) pk = psum_consts(a.vprev);
+    if (!PSUM) {
         const F9 one9 = fr_unpack(fr_one());
         const F9 f = lut9(alut, tid);
         const F9 q = f9_mul(f, f9_sub(f, one9));      // normal, below 2 r
@@ -1313,38 +1390,36 @@ __device__ __forceinline__ void bin3_body(const BinArgs& a, const unsigned bx, c
                 uint32_t clo, chi;
                 pair_codes16(w, j, clo, chi);
                 const F9 bj = sbj[k][j];
-                f9_cols_mac(cols[0], bj, lut9(plut, clo));
-                f9_cols_mac(cols[1], bj, lut9(plut, chi));
+                if (!PSUM) {
+                    f9_cols_mac(cols[0], bj, lut9(plut, clo));
+                    f9_cols_mac(cols[1], bj, lut9(plut, chi));
+                }
                 const F9 d = f9_norm(f9_sub(lut9(alut, chi), lut9(alut, clo)));   // normal, below 6.5 r
                 f9_cols_mac(cols[2], bj, f9_mul(d, d));
                 if (++pending == 4) {
                     pending = 0;
 #pragma unroll
-                    for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
+                    for (int x = (PSUM ? 2 : 0); x < 3; ++x) f9_cols_norm<17>(cols[x]);
                 }
             }
         }
         F9 bi[3];
         beta_line_fold(a, b, m, vprev9, bi);
 #pragma unroll
-        for (int x = 0; x < 3; ++x) f9_cols_norm<17>(cols[x]);
-        // at most 128 products below 2 r^2 each: the reduced sums are normal and below 4.8 r;
-        // below, at most eight such limbs are added between carry passes, and what is
-        // subtracted is below 2.6 r after f9_norm_reduce
-        const F9 sa = f9_norm_reduce(f9_redc(cols[0])), sc = f9_redc(cols[1]), sd = f9_redc(cols[2]);
-        if (a.ps_write) {
-            const uint64_t at = (uint64_t)by * m + b;
-            f9tab_st(a.ps_out[0], at, sa);
-            f9tab_st(a.ps_out[1], at, f9_norm_reduce(sc));
-            f9tab_st(a.ps_out[2], at, f9_norm_reduce(sd));
+        for (int x = (PSUM ? 2 : 0); x < 3; ++x) f9_cols_norm<17>(cols[x]);
+        // at most 128 products below 2 r^2 each: the reduced sums are below 4.8 r before the reducing pass
+        F9 sa, sc;
+        const F9 sd = f9_norm_reduce(f9_redc(cols[2]));
+        if (PSUM) {
+            sa = f9_zero();
+            sc = f9_zero();
+            if (chunk == 0 && k0 == 0) psum_bind(a, b, m, pk, sa, sc);
+        } else {
+            sa = f9_norm_reduce(f9_redc(cols[0]));
+            sc = f9_norm_reduce(f9_redc(cols[1]));
         }
-        const F9 sc2 = f9_add(sc, sc), sd2 = f9_add(sd, sd);
-        const F9 g2 = f9_norm(f9_sub(f9_add(sc2, sd2), sa));                             // -SA + 2 SC + 2 SD
-        const F9 h3 = f9_norm(f9_add(f9_add(sc2, sc), f9_add(sd2, sd2)));                // 3 SC + 4 SD
-        const F9 g3 = f9_norm(f9_sub(f9_sub(f9_add(h3, sd2), sa), sa));                  // ... + 2 SD - 2 SA
-        tot[0] = f9_norm_reduce(f9_add(tot[0], f9_mul(bi[0], sa)));
-        tot[1] = f9_norm_reduce(f9_add(tot[1], f9_mul(bi[1], g2)));
-        tot[2] = f9_norm_reduce(f9_add(tot[2], f9_mul(bi[2], g3)));
+        if (a.ps_write) psum_store(a, (uint64_t)by * m + b, sa, sc, sd);
+        psum_accumulate(tot, bi, sa, sc, sd);
     }
     const uint64_t blk = (uint64_t)by * gx + bx;
     {
@@ -1511,15 +1586,10 @@ __device__ __forceinline__ void binl_body(const BinArgs& a, const unsigned bx, c
     }
 }
 
-// The same rounds when the previous round left its column sums (SA, SC, SD) per pair index.
-// A pair of this round folds two pairs of the previous one (b and b + m of its 2m), and
-//   q_j(X) = (1 - X) p(lo_j) + X p(hi_j) - X (1 - X) (hi_j - lo_j)^2
-// summed over the columns at X = v (the challenge just bound) is what p of the folded entries
-// sums to: SA' = (1 - v) SA_b + v SC_b - v (1 - v) SD_b, SC' the same at b + m.  Only
-// SD' = sum_j beta_J (hi'_j - lo'_j)^2 needs the columns: one square per column instead of
-// three, one accumulator instead of three.  G(0) = SA', G(2) = -SA' + 2 SC' + 2 SD',
-// G(3) = -2 SA' + 3 SC' + 6 SD'.  With the columns cut into chunks, the thread of the first
-// chunk (and slice) takes SA' and SC', adding up the previous round's chunks.
+// The same rounds when the previous round left its column sums (psum_bind): only
+// SD' = sum_j beta_J (hi'_j - lo'_j)^2 needs the columns, one square per column instead of three and
+// one accumulator instead of three.  With the columns cut into chunks, the thread of the first
+// chunk (and slice) takes SA' and SC'.
 template <bool FOLD>
 __device__ __forceinline__ void binp_body(const BinArgs& a, const unsigned bx, const unsigned by, const unsigned gx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
@@ -1533,13 +1603,8 @@ __device__ __forceinline__ void binp_body(const BinArgs& a, const unsigned bx, c
     }
     __syncthreads();
     const uint64_t m = a.m;
-    const F9 v = fr_unpack(*a.vprev);     // the challenge that this round binds on the way
-    F9 u1, nvv;                           // 1 - v, v^2 - v
-    {
-        const Fr vf = *a.vprev;
-        u1 = fr_unpack(fr_sub(fr_one(), vf));
-        nvv = fr_unpack(fr_sub(fr_sqr(vf), vf));
-    }
+    const PsumConsts pk = psum_consts(a.vprev);
+    const F9 v = pk.v;                    // the challenge that this round binds on the way
     const unsigned chunk = a.ksplit ? by >> 1 : by;
     const int k0 = a.ksplit ? (int)(by & 1) : 0, k1 = a.ksplit ? k0 + 1 : (a.has_ga ? 2 : 1);
     int j0 = chunk * a.jc, j1 = j0 + a.jc;
@@ -1581,41 +1646,11 @@ __device__ __forceinline__ void binp_body(const BinArgs& a, const unsigned bx, c
         f9_cols_norm<17>(cols);
         const F9 sd = f9_norm_reduce(f9_redc(cols));   // at most 128 products below 2 r^2: below 4.8 r before
         F9 sa = f9_zero(), sc = f9_zero();
-        if (chunk == 0 && k0 == 0) {
-            // the sums that the previous round left for its pairs b and b + m (2m pairs there)
-            F9 in[2][3];
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int q = 0; q < 3; ++q) in[h][q] = f9_zero();
-            for (int c = 0; c < a.ps_in_chunks; ++c) {
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int q = 0; q < 3; ++q)
-                        in[h][q] = f9_norm_reduce(f9_add(in[h][q], f9tab_ld(a.ps_in[q], (uint64_t)c * 2 * m + b + h * m)));
-            }
-            // three products below 2.41 r^2 each: normal and below 2.41 r after the reducing pass
-            sa = f9_norm_reduce(f9_add(f9_add(f9_mul(u1, in[0][0]), f9_mul(v, in[0][1])), f9_mul(nvv, in[0][2])));
-            sc = f9_norm_reduce(f9_add(f9_add(f9_mul(u1, in[1][0]), f9_mul(v, in[1][1])), f9_mul(nvv, in[1][2])));
-        }
-        if (a.ps_write) {
-            const uint64_t at = (uint64_t)by * m + b;
-            f9tab_st(a.ps_out[0], at, sa);
-            f9tab_st(a.ps_out[1], at, sc);
-            f9tab_st(a.ps_out[2], at, sd);
-        }
+        if (chunk == 0 && k0 == 0) psum_bind(a, b, m, pk, sa, sc);
+        if (a.ps_write) psum_store(a, (uint64_t)by * m + b, sa, sc, sd);
         F9 bi[3];
         beta_line_fold(a, b, m, v, bi);
-        // limbs of sa, sc, sd are below 2^29: at most eight are added between carry passes; what is
-        // subtracted is below 2.6 r
-        const F9 sc2 = f9_add(sc, sc), sd2 = f9_add(sd, sd);
-        const F9 g2 = f9_norm(f9_sub(f9_add(sc2, sd2), sa));                             // -SA + 2 SC + 2 SD
-        const F9 h3 = f9_norm(f9_add(f9_add(sc2, sc), f9_add(sd2, sd2)));                // 3 SC + 4 SD
-        const F9 g3 = f9_norm(f9_sub(f9_sub(f9_add(h3, sd2), sa), sa));                  // ... + 2 SD - 2 SA
-        tot[0] = f9_norm_reduce(f9_add(tot[0], f9_mul(bi[0], sa)));
-        tot[1] = f9_norm_reduce(f9_add(tot[1], f9_mul(bi[1], g2)));
-        tot[2] = f9_norm_reduce(f9_add(tot[2], f9_mul(bi[2], g3)));
+        psum_accumulate(tot, bi, sa, sc, sd);
     }
     const uint64_t blk = (uint64_t)by * gx + bx;
     {
@@ -1637,8 +1672,8 @@ struct ZkRoundArgs {
 };
 
 // MODE 0: first round; 1, 2, 5: rounds 1, 2, 3 on the integers; 3: first round on the columns
-// in memory; 4: later rounds (fold the columns with the previous challenge first); 6, 7: as 3, 4
-// with the column sums of the previous round at hand
+// in memory; 4: later rounds (fold the columns with the previous challenge first); 6, 7, 8, 9: as 3,
+// 4, 2, 5 with the column sums of the previous round at hand
 template <int MODE>
 __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     if (blockIdx.x < a.nb_lin) {
@@ -1653,9 +1688,9 @@ __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     const unsigned bx = bid % a.bin_gx, by = bid / a.bin_gx;
     if (MODE == 0) bin0_body(a.bin, bx, a.bin_gx);
     else if (MODE == 1) bin1_body(a.bin, bx, a.bin_gx);
-    else if (MODE == 2) bin2_body(a.bin, bx, by, a.bin_gx);
-    else if (MODE == 5) bin3_body(a.bin, bx, by, a.bin_gx);
-    else if (MODE >= 6) binp_body<MODE == 7>(a.bin, bx, by, a.bin_gx);
+    else if (MODE == 2 || MODE == 8) bin2_body<MODE == 8>(a.bin, bx, by, a.bin_gx);
+    else if (MODE == 5 || MODE == 9) bin3_body<MODE == 9>(a.bin, bx, by, a.bin_gx);
+    else if (MODE == 6 || MODE == 7) binp_body<MODE == 7>(a.bin, bx, by, a.bin_gx);
     else binl_body<MODE == 4>(a.bin, bx, by, a.bin_gx);
 }
 
@@ -2008,11 +2043,11 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     // split: packed H and L of the five points, then as lazy limbs H, H folded once, L
     const uint64_t split_words = 5 * (nh + nl) * 8 + 5 * (nh + (nh + 1) / 2 + nl) * 9;
     void* beta_mem = zk_alloc(ctx, split ? split_words * 4 : (uint64_t)5 * D * 32);
-    // column sums handed from round to round (from round 3 on): two sets of three tables; a round
+    // column sums handed from round to round (from round 1 on): two sets of three tables; a round
     // with c chunks of m pairs leaves c m entries, and chunks appear only below the fill threshold
     const uint64_t fill_threads = ctx->zk_fill_threads ? ctx->zk_fill_threads : 1;
     constexpr unsigned PS_MAX_CHUNKS = 4;
-    const uint64_t ps_cap = li >= 4 ? ((D >> 4) > 4 * fill_threads ? (D >> 4) : 4 * fill_threads) : 0;
+    const uint64_t ps_cap = li >= 4 ? ((D >> 2) > 4 * fill_threads ? (D >> 2) : 4 * fill_threads) : 0;
     void* ps_mem = ps_cap ? zk_alloc(ctx, 6 * ps_cap * 36) : nullptr;
     if (!mem || !beta_mem || (ps_cap && !ps_mem)) {
         zk_free(ctx, mem);
@@ -2211,11 +2246,11 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         const unsigned nb_bin = bx * chunks;
         ba.jc = jc;
         ba.chal = t == 0 ? nullptr : t < mat_bound ? &st->chal[c_v] : t > mat_bound ? &st->chal[c_v + t - 1] : nullptr;
-        // column sums: round 3 on the integers and the rounds on the columns that use them leave
-        // theirs for the next round, as long as the columns are cut into few chunks
-        const bool ps_ok = mat_bound == 4 && t >= 3 && chunks <= PS_MAX_CHUNKS && (uint64_t)chunks * m <= ps_cap;
-        const bool ps_use = ps_ok && t >= mat_bound && ps_prev_chunks != 0;
-        const bool ps_produce = ps_ok && (t == 3 || ps_use);
+        // column sums: rounds 1 and 3 compute theirs in full, a round that uses the previous round's
+        // leaves its own for the next, as long as the columns are cut into few chunks
+        const bool ps_ok = mat_bound == 4 && t >= 1 && chunks <= PS_MAX_CHUNKS && (uint64_t)chunks * m <= ps_cap;
+        const bool ps_use = ps_ok && t >= 2 && ps_prev_chunks != 0;
+        const bool ps_produce = ps_ok && (t == 1 || t == 3 || ps_use);
         for (int q = 0; q < 3; ++q) {
             ba.ps_in[q] = ps_tab[(t + 1) & 1][q];
             ba.ps_out[q] = ps_tab[t & 1][q];
@@ -2237,8 +2272,13 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, bytes);
         if (t == 0) launch_zk_round<0>(ctx, ra, nb_bin);
         else if (t == 1) launch_zk_round<1>(ctx, ra, nb_bin);
-        else if (t == 2) launch_zk_round<2>(ctx, ra, nb_bin);
-        else if (t < mat_bound) launch_zk_round<5>(ctx, ra, nb_bin);
+        else if (t == 2) {
+            if (ps_use) launch_zk_round<8>(ctx, ra, nb_bin);
+            else launch_zk_round<2>(ctx, ra, nb_bin);
+        } else if (t < mat_bound) {
+            if (ps_use) launch_zk_round<9>(ctx, ra, nb_bin);
+            else launch_zk_round<5>(ctx, ra, nb_bin);
+        }
         else if (t == mat_bound && ps_use) launch_zk_round<6>(ctx, ra, nb_bin);
         else if (t == mat_bound) launch_zk_round<3>(ctx, ra, nb_bin);
         else if (ps_use) launch_zk_round<7>(ctx, ra, nb_bin);
