@@ -328,9 +328,8 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_pe_inner(PeArgs p) {
 //
 // Fr source: sum_a beta_a T_a, 81 multiply-adds per element, both in Montgomery form, so the
 // reduced sum is the Montgomery form of the result.
-// int32 source: x_a is a plain integer: 9 multiply-adds per element into a positive or a
-// negative column set by the sign of x_a; V = P - N is already "beta times integer", so each
-// side is reduced (divide by 2^261) and multiplied back by 2^522 mod r.
+// (int32 sources: k_pe_mid_i32 and k_pe_inner_i32_lazy below; there x_a is a plain integer, nine
+// multiply-adds per element, and the sum is "beta times integer" already.)
 template <int KIND>
 __global__ __launch_bounds__(ZK_BLOCK) void k_pe_mid_lazy(PeArgs p) {
     const uint64_t n_out = p.O * p.I;
@@ -358,31 +357,78 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_pe_mid_lazy(PeArgs p) {
             }
             f9_cols_norm<17>(c);
             res = f9_to_fr(f9_norm_reduce(f9_redc(c)));
-        } else {
-            uint64_t cp[17], cn[17];
-#pragma unroll
-            for (int k = 0; k < 17; ++k) cp[k] = cn[k] = 0;
-            int pending = 0;
-            const int32_t* src = (const int32_t*)p.src;
-            for (uint64_t a = a0; a < a1; ++a) {
-                const F9 b9 = fr_unpack(tab_ld(p.beta, a));
-                const int32_t x = src[(o * p.A + a) * p.I + i];
-                const uint32_t xp = x > 0 ? (uint32_t)x : 0u, xn = x < 0 ? (uint32_t)0 - (uint32_t)x : 0u;
-                f9_cols_mac_small(cp, b9, xp);
-                f9_cols_mac_small(cn, b9, xn);
-                if (++pending == 4) {
-                    pending = 0;
-                    f9_cols_norm<10>(cp);
-                    f9_cols_norm<10>(cn);
-                }
-            }
-            f9_cols_norm<10>(cp);
-            f9_cols_norm<10>(cn);
-            const F9 r2 = fr_unpack(fr_const(frc::R2));
-            const F9 mp = f9_mul(f9_redc(cp), r2), mn = f9_mul(f9_redc(cn), r2);   // both normal, below 2r
-            res = f9_to_fr(f9_sub(mp, mn));
         }
         tab_st(p.out, (uint64_t)blockIdx.y * n_out + e, res);
+    }
+}
+
+// Middle axis contracted, int32 source: thread = output (o, i), block = 256 consecutive outputs.
+// beta of the chunk is unpacked once per block into LDS (every thread reads the same entry of an
+// iteration); the integers of eight rows are requested together before they are used; the
+// products beta_a x_a (29-bit limb by signed 32-bit integer) are added into ten signed 64-bit
+// columns, carried every fourth element.  The sum is "beta times integer", a Montgomery form
+// already: an offset 2^56 2^261 makes it non-negative, it is reduced (divide by 2^261),
+// multiplied back by 2^522 mod r, and the offset's residue is taken off again.
+constexpr int PE_MID_TILE = 256;
+__global__ __launch_bounds__(ZK_BLOCK) void k_pe_mid_i32(PeArgs p) {
+    __shared__ uint32_t sb[9][PE_MID_TILE];
+    const uint64_t n_out = p.O * p.I;
+    const uint64_t a0 = (uint64_t)blockIdx.y * p.a_chunk;
+    uint64_t a1 = a0 + p.a_chunk;
+    if (a1 > p.A) a1 = p.A;
+    const int32_t* src = (const int32_t*)p.src;
+    const uint64_t nblk = (n_out + ZK_BLOCK - 1) / ZK_BLOCK;
+    for (uint64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+        const uint64_t e = blk * ZK_BLOCK + threadIdx.x;
+        const bool live = e < n_out;
+        const uint64_t o = live ? e / p.I : 0, i = live ? e - o * p.I : 0;
+        const int32_t* col = src + (o * p.A) * p.I + i;
+        int64_t c[10];
+#pragma unroll
+        for (int k = 0; k < 10; ++k) c[k] = 0;
+        for (uint64_t at = a0; at < a1; at += PE_MID_TILE) {
+            const int na = (int)(a1 - at < PE_MID_TILE ? a1 - at : PE_MID_TILE);
+            __syncthreads();   // the previous tile is no longer read
+            if ((int)threadIdx.x < na) {
+                const F9 b9 = fr_unpack(tab_ld(p.beta, at + threadIdx.x));
+#pragma unroll
+                for (int l = 0; l < 9; ++l) sb[l][threadIdx.x] = b9.v[l];
+            }
+            __syncthreads();
+            if (live) {
+                for (int k0 = 0; k0 < na; k0 += 8) {
+                    int32_t x[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) x[u] = k0 + u < na ? col[(at + k0 + u) * p.I] : 0;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int k = k0 + u < na ? k0 + u : 0;
+#pragma unroll
+                        for (int l = 0; l < 9; ++l) c[l] += (int64_t)(int32_t)sb[l][k] * (int64_t)x[u];
+                        if ((u & 3) == 3) {   // four products below 2^60 in magnitude per column
+#pragma unroll
+                            for (int l = 0; l + 1 < 10; ++l) {
+                                c[l + 1] += c[l] >> 29;
+                                c[l] &= (int64_t)frc::M29;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        if (live) {
+            // |sum| < 2^286 (chunk length), chunks of at most 2^27 entries: with the offset the top column is positive
+            uint64_t cols[17];
+#pragma unroll
+            for (int k = 0; k < 17; ++k) cols[k] = k < 10 ? (uint64_t)c[k] : 0;
+            cols[9] += (uint64_t)1 << 56;
+            const F9 r2 = fr_unpack(fr_const(frc::R2));
+            F9 off = f9_zero();
+            off.v[1] = 1u << 27;                                  // 2^56 as plain limbs
+            const F9 koff = f9_mul(off, r2);                      // 2^56 2^261 mod r (up to a multiple of r), below 2r
+            const F9 val = f9_mul(f9_redc(cols), r2);             // normal, below 2r
+            tab_st(p.out, (uint64_t)blockIdx.y * n_out + e, f9_to_fr(f9_sub(val, koff)));
+        }
     }
 }
 
@@ -450,8 +496,10 @@ template <int KIND>
 static void launch_pe(zkdl_ctx* ctx, bool inner, const PeArgs& p, dim3 grid) {
     if (inner)
         hipLaunchKernelGGL(k_pe_inner<KIND>, grid, dim3(ZK_BLOCK), 0, ctx->stream, p);
-    else if ((KIND == TK_FR || KIND == TK_I32) && p.a_chunk <= PE_LAZY_MAX_CHUNK)
-        hipLaunchKernelGGL(k_pe_mid_lazy<KIND>, grid, dim3(ZK_BLOCK), 0, ctx->stream, p);
+    else if (KIND == TK_I32)
+        hipLaunchKernelGGL(k_pe_mid_i32, grid, dim3(ZK_BLOCK), 0, ctx->stream, p);
+    else if (KIND == TK_FR && p.a_chunk <= PE_LAZY_MAX_CHUNK)
+        hipLaunchKernelGGL(k_pe_mid_lazy<TK_FR>, grid, dim3(ZK_BLOCK), 0, ctx->stream, p);
     else
         hipLaunchKernelGGL(k_pe_mid<KIND>, grid, dim3(ZK_BLOCK), 0, ctx->stream, p);
 }
