@@ -13,17 +13,23 @@
 //    (lin_body): beta*Z, beta*(1-sign)*Z', beta*G_A, beta*(1-sign)*G_A'.
 //  * Only the binarity terms need the D x (Q+R) tables (bin*_body).  Their
 //    equality factor splits as beta~(u_bin,(i,j)) = beta_I(i) beta_J(j).
-//    Rounds 0, 1 and 2 work on the integers directly: aux is binary, so in round 0
-//    a(x)^2 - a(x) = (x^2 - x) [bit_lo != bit_hi]; after the first challenge an
-//    entry is one of {0, 1, v, 1-v} and round 1 a quadratic form in bits: masked sums of
-//    beta_J and five products (bin1_body); after the second it is one of 16 values and a pair one of 256
-//    combinations, so round 2 reads q(x) from a 256-entry table (bin2_body).
-//    After the third challenge the columns are written out once (k_zk_mat3, one of
-//    256 values per entry), column-major: entry (k, j, i) at plane (k*(Q+R)+j), so
-//    that threads over i read coalesced limb planes; D/8 rows.  Later rounds fold them
-//    (binl_body).  sum_j beta_J(j) q_j(x) is accumulated as 64-bit columns and reduced
-//    once per pair index; beta_I is folded by the binarity blocks themselves between
+//    Rounds 0 to 3 work on the integers directly: aux is binary, so in round 0
+//    a(x)^2 - a(x) = (x^2 - x) [bit_lo != bit_hi]; with t challenges bound an entry is a
+//    combination of 2^t bits whose coefficients add up to one, which makes round 1 a
+//    quadratic form in the bits: masked sums of beta_J and five products (bin1_body);
+//    rounds 2 and 3 read an entry's value from a 16- / 256-entry table by its bits
+//    (bin2_body, bin3_body).  After the fourth challenge the columns are written out
+//    once (k_zk_mat4), column-major: entry (k, j, i) at plane (k*(Q+R)+j), so
+//    that threads over i read coalesced limb planes; D/16 rows.  Later rounds fold them
+//    (binp_body, binl_body).  Sums over j of beta_J(j) (...) are accumulated as 64-bit columns
+//    and reduced once per pair index.  From round 1 on a round leaves its column sums
+//    SA, SC, SD per pair index for the next one (psum_bind), which then squares only
+//    hi - lo per column.  beta_I is folded by the binarity blocks themselves between
 //    two buffers, so they share no table with the linear blocks.
+//  * The first two rounds of the linear equations and the input claims read the integers
+//    (9 x 2 limb products, no value tables before round 1: lin0_int_body, lin1_int_body,
+//    k_zk_prepare_int) and take the equality tables over i as products of two factors of
+//    about sqrt(D) entries (SplitEq); round 1 writes all folded tables for the later rounds.
 //  * One launch per i-round (k_zk_round): the first blocks take the linear equations,
 //    the others the binarity terms; the round's finaliser adds up all partial sums.
 //    Rounds with few pairs spread a pair over more threads (lin_body_small, column
@@ -900,7 +906,7 @@ __device__ __forceinline__ void bin0_body(const BinArgs& a, const unsigned bx, c
     else if (tid < 4) p[tid - 2] = fr_zero();
 }
 
-// ---- rounds >= 1 work on field elements; the first two challenges are bound by table look-up ----
+// ---- rounds >= 1 work on field elements; the first challenges are bound by table look-up ----
 //
 // aux is binary, so after binding x0 = v0 an entry is one of four values, selected by the
 // two bits it interpolates: A(b_lo, b_hi) = b_lo + v0 (b_hi - b_lo), code = b_lo + 2 b_hi:
@@ -1260,8 +1266,9 @@ __device__ __forceinline__ void bin2_body(const BinArgs& a, const unsigned bx, c
     }
 }
 
-// After the third challenge: entry (k, v0, v1, v2, i3, j) = lo + v2 (hi - lo), one of 256
-// values by the eight bits; written as lazy limbs, D/8 rows per column.
+// After the third challenge (8 <= D < 16 only; larger D write their columns after the fourth):
+// entry (k, v0, v1, v2, i3, j) = lo + v2 (hi - lo), one of 256 values by the eight bits; written
+// as lazy limbs, D/8 rows per column.
 __global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat3(BinArgs a) {
     __shared__ F9 val16[16];
     __shared__ uint32_t vlut[9][256];
