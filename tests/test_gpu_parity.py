@@ -553,6 +553,32 @@ def test_config3_aggregate_by_properties(lib, ctx):
     fproof, fpts = res["fwd"]
     vn, vi = fpts["v"][:3], fpts["v"][3:]
     assert fproof.finals[1] == mle_eval(fr_array(wit["A"]), vn + fpts["u0"] + vi)
+    # zkReLU at full size (D = 2^19 rows): the four input claims are the MLEs of Z, A = relu(Z'),
+    # G_A and (1 - sign) G_A' at their points, and the one claim left on aux after the merge is
+    # aux~(k*, v, w*) evaluated directly from the bits of the witness
+    from oracle.mle import beta_table
+    zk = res["zkrelu"]
+    z = wit["Zr"].reshape(-1).astype(object)
+    ga = wit["GA"].reshape(-1).astype(object)
+    q_bits, r_bits = wit["Q"], wit["R"]
+    half = 1 << (r_bits - 1)
+    ns = np.array([0 if int(x) < 0 else 1 for x in z], dtype=object)
+    zp = np.array([(int(x) + half) >> r_bits for x in z], dtype=object)
+    gp = np.array([(int(x) + half) >> r_bits for x in ga], dtype=object)
+    pts = zk["points"]
+    for claim, vec, pt in ((zk["c_in"][0], z, pts["u_z"]), (zk["c_in"][1], ns * zp, pts["u_a"]),
+                           (zk["c_in"][2], ga, pts["u_ga"]), (zk["c_in"][3], ns * gp, pts["u_gz"])):
+        assert claim == int(np.dot(beta_table(pt), vec % R_MOD) % R_MOD)
+    li = len(pts["u_z"])
+    point, value = zk["aux_claim"]["point"], zk["aux_claim"]["value"]
+    kst, v_i, wst = point[0], point[1:1 + li], point[1 + li:]
+    b_i, b_j = beta_table(v_i), beta_table(wst)
+    total = 0
+    for bk, arr in (((1 - kst) % R_MOD, wit["Zr"].reshape(-1)), (kst, wit["GA"].reshape(-1))):
+        for j in range(q_bits + r_bits):
+            mask = ((arr >> j) & 1).astype(bool)
+            total += bk * int(b_j[j]) % R_MOD * int(b_i[mask].sum() % R_MOD)
+    assert value == total % R_MOD
 
 
 @pytest.mark.parametrize("name,layers,width,batch,steps,cfg", [
