@@ -90,7 +90,7 @@ int zkdl_ctx_create(zkdl_ctx** out, int device, void* hip_stream);
 int zkdl_ctx_destroy(zkdl_ctx* ctx);
 int zkdl_last_hip_error(const zkdl_ctx* ctx);
 /* Tuning: zkrelu_prove cuts the bit columns of a round into chunks (more threads per row pair)
- * until about `threads` threads are busy; the default, 131072, is two waves on every SIMD of the
+ * until about `threads` threads are busy; the default, 65536, is one wave on every SIMD of the
  * device.  Proofs do not depend on it.  1 <= threads <= 2^24, else ZKDL_EINVAL. */
 int zkdl_ctx_set_fill_threads(zkdl_ctx* ctx, uint64_t threads);
 const char* zkdl_strerror(int err);

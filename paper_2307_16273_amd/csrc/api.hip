@@ -132,7 +132,7 @@ extern "C" int zkdl_ctx_create(zkdl_ctx** out, int device, void* hip_stream) {
     ctx->n_chal = 0;
     ctx->proof_len = 0;
     ctx->prof_on = false;
-    ctx->zk_fill_threads = 131072;   // two waves on each of the 1024 SIMDs
+    ctx->zk_fill_threads = 65536;    // one wave on each of the 1024 SIMDs; measured best on the 8 x 1024^2 network
     ctx->prof_used = 0;
     for (int i = 0; i < ZKDL_PROF_CLASSES; ++i) {
         ctx->prof_ms[i] = ctx->prof_bytes[i] = 0.0;

@@ -2166,7 +2166,8 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     pa.sp = sp0;
     pa.part = ctx->partials;
     pa.st = st;
-    unsigned nb = blocks_for(D, ZK_MAX_PART_BLOCKS);
+    // the integer kernel pays eight products per thread when a run ends: at least eight rows per thread
+    unsigned nb = lin_from_ints ? blocks_for((D + 7) / 8, ZK_MAX_PART_BLOCKS) : blocks_for(D, ZK_MAX_PART_BLOCKS);
     if (lin_from_ints) hipLaunchKernelGGL(k_zk_prepare_int, dim3(nb), dim3(ZK_BLOCK), 0, ctx->stream, pa);
     else hipLaunchKernelGGL(k_zk_prepare, dim3(nb), dim3(ZK_BLOCK), 0, ctx->stream, pa);
     ClaimsArgs ca;
@@ -2240,7 +2241,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         // few rows: split the columns over more blocks (rounds on the 64-bit words take them whole)
         // Every (pair index, chunk) thread pays the beta_I fold and three reductions on top of its
         // columns, about as much as one column costs: split only until the machine is full
-        // (two waves per SIMD: 2^17 threads).
+        // (the context's fill threshold, by default one wave per SIMD).
         const uint64_t ZK_FILL_THREADS = fill_threads;
         int jc = nbits;
         if (t >= 2)
