@@ -1475,6 +1475,172 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat4(BinArgs a) {
     }
 }
 
+// ---- round 4 from the integers; the columns are written after the fifth challenge ----------
+// Taken when the column sums reach round 4 and its columns are not cut into chunks (large D): the
+// round then needs only sum_j beta_J (hi_j - lo_j)^2, and an entry with four challenges bound is
+// (1 - v3) A[c_lo] + v3 A[c_hi] by the 16 bits it interpolates (as in k_zk_mat4), so nothing has to
+// be in memory yet and the columns are written with half the rows once more.  The rows of pair
+// index i5 (m = D/32 of them) are i5 + s m, s = 16 x0 + 8 x1 + 4 x2 + 2 x3 + x4.  Bit j of all 32
+// rows is wanted for every column j: the 32 x 64 bit matrix of the rows is transposed once (two
+// 32 x 32 blocks, five swap stages each), with the rows ordered so that the four codes of a
+// column are the four bytes of its word.
+
+// in-place transpose of a 32 x 32 bit matrix: afterwards bit p of a[j] is what bit j of a[p] was
+__device__ __forceinline__ void transpose32(uint32_t a[32]) {
+#pragma unroll
+    for (int s = 0; s < 5; ++s) {
+        const int j = 16 >> s;
+        const uint32_t m = s == 0 ? 0x0000FFFFu : s == 1 ? 0x00FF00FFu : s == 2 ? 0x0F0F0F0Fu : s == 3 ? 0x33333333u : 0x55555555u;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            if (k & j) continue;
+            const uint32_t t = ((a[k] >> j) ^ a[k + j]) & m;
+            a[k] ^= t << j;
+            a[k + j] ^= t;
+        }
+    }
+}
+
+// Row that lands in bit p of a column's word: byte g = 2 x4 + x3 holds the code (bit order of
+// pair_code8) of the eight rows with that (x3, x4).
+__device__ __forceinline__ int bin4_row_of_bit(int p) {
+    const int order8[8] = {0, 4, 2, 6, 1, 5, 3, 7};
+    const int g = p >> 3, q = p & 7;
+    return 4 * order8[q] + 2 * (g & 1) + (g >> 1);
+}
+
+// words of 32 columns (bit p = bit j of row bin4_row_of_bit(p)), columns 32 half .. 32 half + 31,
+// left in the thread's own slots cw[.][threadIdx.x]: the column loop then runs over j without
+// being unrolled (no barrier is needed, no thread reads another's slots)
+__device__ __forceinline__ void bin4_columns(const int64_t* src, uint64_t b, uint64_t m, int half, uint32_t (*cw)[ZK_BLOCK]) {
+    uint32_t a32[32];
+#pragma unroll
+    for (int p = 0; p < 32; ++p) {
+        const uint64_t w = (uint64_t)src[b + (uint64_t)bin4_row_of_bit(p) * m];
+        a32[p] = half ? (uint32_t)(w >> 32) : (uint32_t)w;
+    }
+    transpose32(a32);
+#pragma unroll
+    for (int p = 0; p < 32; ++p) cw[p][threadIdx.x] = a32[p];
+}
+
+struct Bin4Luts {
+    uint32_t lut0[9][256];   // (1 - v3) A[c], fully reduced; A[c]: the entry with three challenges bound
+    uint32_t lut1[9][256];   // v3 A[c], fully reduced
+};
+
+// scratch: 9 x 256 words that are free until the tables are built (all threads; ends with a barrier)
+__device__ __forceinline__ void bin4_luts_build(const Fr* chal, F9* val16, uint32_t (*scratch)[256], Bin4Luts& L) {
+    bound3_values(chal, val16, scratch);
+    const int tid = threadIdx.x;
+    const Fr v3 = chal[3], u3 = fr_sub(fr_one(), v3);
+    const F9 f = lut9(scratch, tid);     // the thread's own entry
+    const F9 f0 = f9_cond_sub(f9_mul(fr_unpack(u3), f)), f1 = f9_cond_sub(f9_mul(fr_unpack(v3), f));
+#pragma unroll
+    for (int l = 0; l < 9; ++l) {
+        L.lut0[l][tid] = f0.v[l];
+        L.lut1[l][tid] = f1.v[l];
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ void bin4_body(const BinArgs& a, const unsigned bx, const unsigned gx) {
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    __shared__ F9 sbj[2][64];
+    __shared__ F9 val16[16];
+    __shared__ Bin4Luts L;
+    __shared__ uint32_t cw[32][ZK_BLOCK];   // a thread's column words, 32 columns at a time
+    const int tid = threadIdx.x;
+    if (tid < 128) {
+        const int j = tid & 63, k = tid >> 6;
+        F9 x = f9_zero();
+        if (j < a.nbits) x = fr_unpack(k == 0 ? a.bJ[j] : fr_mul(*a.rp, a.bJ[j]));
+        sbj[k][j] = x;
+    }
+    bin4_luts_build(a.chal, val16, (uint32_t (*)[256])&cw[0][0], L);
+    const PsumConsts pk = psum_consts(a.vprev);
+    const uint64_t m = a.m;
+    F9 tot[3];
+#pragma unroll
+    for (int x = 0; x < 3; ++x) tot[x] = f9_zero();
+    for (uint64_t b = bx * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gx * blockDim.x) {
+        uint64_t cols[17];
+#pragma unroll
+        for (int c = 0; c < 17; ++c) cols[c] = 0;
+        int pending = 0;
+        for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+            for (int half = 0; 32 * half < a.nbits; ++half) {
+                bin4_columns(k == 0 ? a.z : a.ga, b, m, half, cw);
+                const int jn = a.nbits - 32 * half < 32 ? a.nbits - 32 * half : 32;
+                for (int jj = 0; jj < jn; ++jj) {
+                    const uint32_t w = cw[jj][tid];
+                    // entries at x4 = 0 (bytes 0, 1) and x4 = 1 (bytes 2, 3), each below 2 r
+                    const F9 e0 = f9_norm(f9_add(lut9(L.lut0, w & 255), lut9(L.lut1, (w >> 8) & 255)));
+                    const F9 e1 = f9_add(lut9(L.lut0, (w >> 16) & 255), lut9(L.lut1, w >> 24));
+                    const F9 d = f9_norm(f9_sub(e1, e0));     // limbs of e1 below 2^30; normal, below 6 r
+                    f9_cols_mac(cols, sbj[k][32 * half + jj], f9_mul(d, d));
+                    if (++pending == 4) {
+                        pending = 0;
+                        f9_cols_norm<17>(cols);
+                    }
+                }
+            }
+        }
+        f9_cols_norm<17>(cols);
+        const F9 sd = f9_norm_reduce(f9_redc(cols));
+        F9 sa, sc;
+        psum_bind(a, b, m, pk, sa, sc);
+        if (a.ps_write) psum_store(a, b, sa, sc, sd);
+        F9 bi[3];
+        beta_line_fold(a, b, m, pk.v, bi);
+        psum_accumulate(tot, bi, sa, sc, sd);
+    }
+    {
+        const Fr s = block_sum_lazy<3>(tot, red);
+        Fr* p = a.part + (uint64_t)bx * 4;
+        if (tid < 3) p[tid ? tid + 1 : 0] = s;
+        else if (tid == 3) p[1] = fr_zero();
+    }
+}
+
+// After the fifth challenge: entry (k, v0..v4, i5, j) = (1 - v4) e0 + v4 e1 with e0, e1 as in
+// bin4_body: four table reads and three additions; lazy limbs (normal, below 2.41 r), D/32 rows.
+__global__ __launch_bounds__(ZK_BLOCK) void k_zk_mat5(BinArgs a) {
+    __shared__ F9 val16[16];
+    __shared__ uint32_t t4[4][9][256];   // (1-v4)(1-v3) A, (1-v4) v3 A, v4 (1-v3) A, v4 v3 A; fully reduced
+    __shared__ uint32_t cw[32][ZK_BLOCK];
+    const int tid = threadIdx.x;
+    {
+        uint32_t (*alut)[256] = (uint32_t (*)[256])&cw[0][0];   // free until the first columns are transposed
+        bound3_values(a.chal, val16, alut);
+        const Fr v3 = a.chal[3], u3 = fr_sub(fr_one(), v3), v4 = a.chal[4], u4 = fr_sub(fr_one(), v4);
+        const F9 f = lut9(alut, tid);   // the thread's own entry
+        const Fr c[4] = {fr_mul(u4, u3), fr_mul(u4, v3), fr_mul(v4, u3), fr_mul(v4, v3)};
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const F9 q = f9_cond_sub(f9_mul(fr_unpack(c[g]), f));
+#pragma unroll
+            for (int l = 0; l < 9; ++l) t4[g][l][tid] = q.v[l];
+        }
+    }
+    __syncthreads();
+    const uint64_t m = a.m;   // rows written = D / 32
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + tid; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+        for (int k = 0; k < (a.has_ga ? 2 : 1); ++k) {
+            for (int half = 0; 32 * half < a.nbits; ++half) {
+                bin4_columns(k == 0 ? a.z : a.ga, b, m, half, cw);
+                const int jn = a.nbits - 32 * half < 32 ? a.nbits - 32 * half : 32;
+                for (int jj = 0; jj < jn; ++jj) {
+                    const uint32_t w = cw[jj][tid];
+                    const F9 e = f9_add(f9_add(lut9(t4[0], w & 255), lut9(t4[1], (w >> 8) & 255)),
+                                        f9_add(lut9(t4[2], (w >> 16) & 255), lut9(t4[3], w >> 24)));
+                    f9tab_st(aux_col9(a, k, 32 * half + jj), b, f9_norm_reduce(e));
+                }
+            }
+        }
+    }
+}
+
 // the raw entries of one column that a pair index needs: (b, b+m), or (b, b+m, b+2m, b+3m)
 // when the previous challenge is still to be bound
 template <bool FOLD>
@@ -1680,7 +1846,7 @@ struct ZkRoundArgs {
 
 // MODE 0: first round; 1, 2, 5: rounds 1, 2, 3 on the integers; 3: first round on the columns
 // in memory; 4: later rounds (fold the columns with the previous challenge first); 6, 7, 8, 9: as 3,
-// 4, 2, 5 with the column sums of the previous round at hand
+// 4, 2, 5 with the column sums of the previous round at hand; 10: round 4 on the integers (with them)
 template <int MODE>
 __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     if (blockIdx.x < a.nb_lin) {
@@ -1698,6 +1864,7 @@ __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     else if (MODE == 2 || MODE == 8) bin2_body<MODE == 8>(a.bin, bx, by, a.bin_gx);
     else if (MODE == 5 || MODE == 9) bin3_body<MODE == 9>(a.bin, bx, by, a.bin_gx);
     else if (MODE == 6 || MODE == 7) binp_body<MODE == 7>(a.bin, bx, by, a.bin_gx);
+    else if (MODE == 10) bin4_body(a.bin, bx, a.bin_gx);
     else binl_body<MODE == 4>(a.bin, bx, by, a.bin_gx);
 }
 
@@ -2036,7 +2203,26 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
 
     // memory: 10 D-sized tables, beta_J, aux columns (2 * nbits columns of 36 B entries; the rows
     // are written once four challenges are bound, D/16 of them; fewer challenges if D < 16)
-    const int mat_bound = li >= 4 ? 4 : li >= 3 ? 3 : 2;
+    // column chunks of round t (m pairs): few rows are split over more threads (rounds 0 and 1 take the
+    // 64-bit words whole); every (pair index, chunk) thread pays the beta_I fold and the reductions on
+    // top of its columns, so only until the machine is full (the context's fill threshold)
+    const uint64_t fill_threads = ctx->zk_fill_threads ? ctx->zk_fill_threads : 1;
+    auto chunks_of = [&](int t, uint64_t m, int* jc_out, int* ksplit_out) -> unsigned {
+        int jc = nbits;
+        if (t >= 2)
+            while ((uint64_t)((nbits + jc - 1) / jc) * m < fill_threads && jc > 1) jc = (jc + 1) / 2;
+        unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
+        // one column per thread and still not full: give the two slices their own threads as well
+        const int ks = (t >= 2 && has_ga && jc == 1 && (uint64_t)chunks * m < fill_threads) ? 1 : 0;
+        if (ks) chunks *= 2;
+        if (jc_out) *jc_out = jc;
+        if (ksplit_out) *ksplit_out = ks;
+        return chunks;
+    };
+    // the columns are written after four challenges, or after five when round 4 can run on the
+    // integers (whole columns per thread, column sums at hand); fewer for D < 16
+    const bool round4_on_ints = li >= 5 && chunks_of(4, D >> 5, nullptr, nullptr) == 1;
+    const int mat_bound = round4_on_ints ? 5 : li >= 4 ? 4 : li >= 3 ? 3 : 2;
     const uint64_t rows = li >= 3 ? D >> mat_bound : 1;
     const uint64_t aux_elems = (uint64_t)(has_ga ? 2 : 1) * nbits * rows;
     const uint64_t alt_rows = D >= 2 ? D / 2 : 1;   // second buffer of the beta_I folds
@@ -2052,7 +2238,6 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     void* beta_mem = zk_alloc(ctx, split ? split_words * 4 : (uint64_t)5 * D * 32);
     // column sums handed from round to round (from round 1 on): two sets of three tables; a round
     // with c chunks of m pairs leaves c m entries, and chunks appear only below the fill threshold
-    const uint64_t fill_threads = ctx->zk_fill_threads ? ctx->zk_fill_threads : 1;
     constexpr unsigned PS_MAX_CHUNKS = 16;   // measured: 4 and 256 are slower (config 3: 2.96 and 5.2 ms against 2.83)
     const uint64_t ps_cap = li >= 4 ? ((D >> 2) > 4 * fill_threads ? (D >> 2) : 4 * fill_threads) : 0;
     void* ps_mem = ps_cap ? zk_alloc(ctx, 6 * ps_cap * 36) : nullptr;
@@ -2238,25 +2423,16 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         ba.vprev = t > 0 ? &st->chal[c_v + t - 1] : nullptr;
         ba.m = m;
         ba.part = ctx->partials + (uint64_t)nb_lin * 4;
-        // few rows: split the columns over more blocks (rounds on the 64-bit words take them whole)
-        // Every (pair index, chunk) thread pays the beta_I fold and three reductions on top of its
-        // columns, about as much as one column costs: split only until the machine is full
-        // (the context's fill threshold, by default one wave per SIMD).
-        const uint64_t ZK_FILL_THREADS = fill_threads;
-        int jc = nbits;
-        if (t >= 2)
-            while ((uint64_t)((nbits + jc - 1) / jc) * m < ZK_FILL_THREADS && jc > 1) jc = (jc + 1) / 2;
-        unsigned chunks = (unsigned)((nbits + jc - 1) / jc);
-        // one column per thread and still not full: give the two slices their own threads as well
-        ba.ksplit = (t >= 2 && has_ga && jc == 1 && (uint64_t)chunks * m < ZK_FILL_THREADS) ? 1 : 0;
-        if (ba.ksplit) chunks *= 2;
+        int jc = nbits, ksplit = 0;
+        const unsigned chunks = chunks_of(t, m, &jc, &ksplit);
+        ba.ksplit = ksplit;
         const unsigned bx = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / chunks);
         const unsigned nb_bin = bx * chunks;
         ba.jc = jc;
         ba.chal = t == 0 ? nullptr : t < mat_bound ? &st->chal[c_v] : t > mat_bound ? &st->chal[c_v + t - 1] : nullptr;
         // column sums: rounds 1 and 3 compute theirs in full, a round that uses the previous round's
         // leaves its own for the next, as long as the columns are cut into few chunks
-        const bool ps_ok = mat_bound == 4 && t >= 1 && chunks <= PS_MAX_CHUNKS && (uint64_t)chunks * m <= ps_cap;
+        const bool ps_ok = mat_bound >= 4 && t >= 1 && chunks <= PS_MAX_CHUNKS && (uint64_t)chunks * m <= ps_cap;
         const bool ps_use = ps_ok && t >= 2 && ps_prev_chunks != 0;
         const bool ps_produce = ps_ok && (t == 1 || t == 3 || ps_use);
         for (int q = 0; q < 3; ++q) {
@@ -2275,7 +2451,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         if (t == 0) bytes += ns * 16.0 * (double)m;
         else if (t == 1) bytes += ns * 32.0 * (double)m;
         else if (t == 2) bytes += ns * 64.0 * (double)m;
-        else if (t < mat_bound) bytes += ns * 128.0 * (double)m;
+        else if (t < mat_bound) bytes += ns * (t == 3 ? 128.0 : 256.0) * (double)m;
         else bytes += ns * nbits * (t > mat_bound ? 216.0 : 72.0) * (double)m;
         zk_prof_begin(ctx, ZKDL_PROF_ZK_BIN, bytes);
         if (t == 0) launch_zk_round<0>(ctx, ra, nb_bin);
@@ -2283,9 +2459,11 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         else if (t == 2) {
             if (ps_use) launch_zk_round<8>(ctx, ra, nb_bin);
             else launch_zk_round<2>(ctx, ra, nb_bin);
-        } else if (t < mat_bound) {
+        } else if (t == 3 && t < mat_bound) {
             if (ps_use) launch_zk_round<9>(ctx, ra, nb_bin);
             else launch_zk_round<5>(ctx, ra, nb_bin);
+        } else if (t < mat_bound) {
+            launch_zk_round<10>(ctx, ra, nb_bin);   // round 4 on the integers: mat_bound = 5 implies ps_use
         }
         else if (t == mat_bound && ps_use) launch_zk_round<6>(ctx, ra, nb_bin);
         else if (t == mat_bound) launch_zk_round<3>(ctx, ra, nb_bin);
@@ -2308,6 +2486,8 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
             ba.m = m;
             if (mat_bound == 2)
                 hipLaunchKernelGGL(k_zk_mat2, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
+            else if (mat_bound == 5)
+                hipLaunchKernelGGL(k_zk_mat5, dim3(blocks_for(m, 16384)), dim3(ZK_BLOCK), 0, ctx->stream, ba);
             else if (mat_bound == 4)
                 hipLaunchKernelGGL(k_zk_mat4, dim3(blocks_for(m, 16384), chunks), dim3(ZK_BLOCK), 0, ctx->stream, ba);
             else
