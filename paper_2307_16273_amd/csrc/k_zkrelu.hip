@@ -248,6 +248,8 @@ struct LinArgs {
     int nbits, r_bits;
     SplitEq sp;            // with from_ints: the equality tables in two factors (H bound as far as the round needs)
     unsigned eq_blocks;    // round 0 with from_ints: blocks per equation (block / eq_blocks = equation)
+    int split_eq;          // the equality tables of this round come from sp (rounds >= 2 as well, value tables in memory)
+    int write_eq;          // ... and are written out folded for the next round, which reads them from memory
 };
 
 // pair (lo, hi) of a lazy table, folded with the previous challenge first when FOLD; both
@@ -263,6 +265,23 @@ __device__ __forceinline__ void lin_pair(const F9Tab& t, uint64_t b, uint64_t m,
     } else {
         lo = f9tab_ld(t, b);
         hi = f9tab_ld(t, b + m);
+    }
+}
+
+// pair (lo, hi) of the equality table of equation e (table `tab` when it lives in memory): from the two
+// factors while the round's variable lies in H (SPLIT), written out only when the next round reads it
+// from memory
+template <bool FOLD, bool SPLIT>
+__device__ __forceinline__ void eq_pair(const LinArgs& a, int e, int tab, uint64_t b, uint64_t m, const F9& v, F9& lo, F9& hi) {
+    if (SPLIT) {
+        lo = split_entry(a.sp.H[e], a.sp.L[e], a.sp.lb, b);
+        hi = split_entry(a.sp.H[e], a.sp.L[e], a.sp.lb, b + m);
+        if (a.write_eq) {
+            f9tab_st(a.tabs.t[tab], b, lo);
+            f9tab_st(a.tabs.t[tab], b + m, hi);
+        }
+    } else {
+        lin_pair<FOLD>(a.tabs.t[tab], b, m, v, lo, hi);
     }
 }
 
@@ -282,7 +301,7 @@ __device__ __forceinline__ void line3(const F9& lo, const F9& hi, F9 e[3]) {
 // Linear equations of one i-round: sum over i' of
 //   (r^2 beta_Z) Z + (r beta_A)(1 - sign) Z' + (r'r^2 beta_GA) G_A + (r'r beta_GZ)(1 - sign) G_A'
 // at x = 0, 2, 3 (x = 1 comes from the claim).
-template <bool FOLD>
+template <bool FOLD, bool SPLIT>
 __device__ __forceinline__ void lin_body(const LinArgs& a, const unsigned bx, const unsigned gx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     F9 acc[3];
@@ -296,13 +315,13 @@ __device__ __forceinline__ void lin_body(const LinArgs& a, const unsigned bx, co
         F9 lo, hi, ns[3], p[3], q[3];
         lin_pair<FOLD>(a.tabs.t[T_NS], b, m, v, lo, hi);
         line3<false>(lo, hi, ns);
-        lin_pair<FOLD>(a.tabs.t[T_BZ], b, m, v, lo, hi);
+        eq_pair<FOLD, SPLIT>(a, 0, T_BZ, b, m, v, lo, hi);
         line3<true>(lo, hi, p);
         lin_pair<FOLD>(a.tabs.t[T_Z], b, m, v, lo, hi);
         line3<false>(lo, hi, q);
 #pragma unroll
         for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
-        lin_pair<FOLD>(a.tabs.t[T_BA], b, m, v, lo, hi);
+        eq_pair<FOLD, SPLIT>(a, 1, T_BA, b, m, v, lo, hi);
         line3<true>(lo, hi, p);
         lin_pair<FOLD>(a.tabs.t[T_ZP], b, m, v, lo, hi);
         line3<false>(lo, hi, q);
@@ -311,13 +330,13 @@ __device__ __forceinline__ void lin_body(const LinArgs& a, const unsigned bx, co
 #pragma unroll
         for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
         if (a.has_ga) {
-            lin_pair<FOLD>(a.tabs.t[T_BGA], b, m, v, lo, hi);
+            eq_pair<FOLD, SPLIT>(a, 2, T_BGA, b, m, v, lo, hi);
             line3<true>(lo, hi, p);
             lin_pair<FOLD>(a.tabs.t[T_GA], b, m, v, lo, hi);
             line3<false>(lo, hi, q);
 #pragma unroll
             for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
-            lin_pair<FOLD>(a.tabs.t[T_BGZ], b, m, v, lo, hi);
+            eq_pair<FOLD, SPLIT>(a, 3, T_BGZ, b, m, v, lo, hi);
             line3<true>(lo, hi, p);
             lin_pair<FOLD>(a.tabs.t[T_GAP], b, m, v, lo, hi);
             line3<false>(lo, hi, q);
@@ -585,10 +604,7 @@ __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned b
         f9tab_st(a.tabs.t[T_NS], b, lo);
         f9tab_st(a.tabs.t[T_NS], b + m, hi);
         line3<false>(lo, hi, ns);
-        lo = split_entry(a.sp.H[0], a.sp.L[0], a.sp.lb, b);
-        hi = split_entry(a.sp.H[0], a.sp.L[0], a.sp.lb, b + m);
-        f9tab_st(a.tabs.t[T_BZ], b, lo);
-        f9tab_st(a.tabs.t[T_BZ], b + m, hi);
+        eq_pair<true, true>(a, 0, T_BZ, b, m, kf[0], lo, hi);
         line3<true>(lo, hi, p);
         lo = fold_ints(kf, r[0].z, r[2].z);
         hi = fold_ints(kf, r[1].z, r[3].z);
@@ -597,10 +613,7 @@ __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned b
         line3<false>(lo, hi, q);
 #pragma unroll
         for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
-        lo = split_entry(a.sp.H[1], a.sp.L[1], a.sp.lb, b);
-        hi = split_entry(a.sp.H[1], a.sp.L[1], a.sp.lb, b + m);
-        f9tab_st(a.tabs.t[T_BA], b, lo);
-        f9tab_st(a.tabs.t[T_BA], b + m, hi);
+        eq_pair<true, true>(a, 1, T_BA, b, m, kf[0], lo, hi);
         line3<true>(lo, hi, p);
         lo = fold_ints(kf, r[0].zp, r[2].zp);
         hi = fold_ints(kf, r[1].zp, r[3].zp);
@@ -614,10 +627,7 @@ __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned b
         if (a.has_ga) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) r[i] = int_row(a.ga[b + i * m], a.nbits, a.r_bits);
-            lo = split_entry(a.sp.H[2], a.sp.L[2], a.sp.lb, b);
-        hi = split_entry(a.sp.H[2], a.sp.L[2], a.sp.lb, b + m);
-        f9tab_st(a.tabs.t[T_BGA], b, lo);
-        f9tab_st(a.tabs.t[T_BGA], b + m, hi);
+            eq_pair<true, true>(a, 2, T_BGA, b, m, kf[0], lo, hi);
             line3<true>(lo, hi, p);
             lo = fold_ints(kf, r[0].z, r[2].z);
             hi = fold_ints(kf, r[1].z, r[3].z);
@@ -626,10 +636,7 @@ __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned b
             line3<false>(lo, hi, q);
 #pragma unroll
             for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
-            lo = split_entry(a.sp.H[3], a.sp.L[3], a.sp.lb, b);
-        hi = split_entry(a.sp.H[3], a.sp.L[3], a.sp.lb, b + m);
-        f9tab_st(a.tabs.t[T_BGZ], b, lo);
-        f9tab_st(a.tabs.t[T_BGZ], b + m, hi);
+            eq_pair<true, true>(a, 3, T_BGZ, b, m, kf[0], lo, hi);
             line3<true>(lo, hi, p);
             lo = fold_ints(kf, r[0].zp, r[2].zp);
             hi = fold_ints(kf, r[1].zp, r[3].zp);
@@ -933,7 +940,7 @@ __device__ __forceinline__ Fr bit_pair_value(int code, const Fr& v, const Fr& on
 // for the next round (every column chunk writes the same values), return the line at 0, 2, 3
 __device__ __forceinline__ void beta_line_fold(const BinArgs& a, uint64_t b, uint64_t m, const F9& vprev, F9 e[3]) {
     F9 lo, hi;
-    if (a.split) {   // round 1: the H factor is folded already
+    if (a.split) {   // the H factor is folded already
         lo = split_entry(a.sH, a.sL, a.s_lb, b);
         hi = split_entry(a.sH, a.sL, a.s_lb, b + m);
     } else {
@@ -1853,8 +1860,9 @@ __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
         if (MODE <= 1 && a.lin.from_ints) {
             if (MODE == 0) lin0_int_body(a.lin, blockIdx.x);
             else lin1_int_body(a.lin, blockIdx.x, a.nb_lin);
-        } else if (a.lin_small) lin_body_small<MODE != 0>(a.lin, blockIdx.x);
-        else lin_body<MODE != 0>(a.lin, blockIdx.x, a.nb_lin);
+        } else if (MODE >= 2 && a.lin.split_eq) lin_body<true, true>(a.lin, blockIdx.x, a.nb_lin);
+        else if (a.lin_small) lin_body_small<MODE != 0>(a.lin, blockIdx.x);
+        else lin_body<MODE != 0, false>(a.lin, blockIdx.x, a.nb_lin);
         return;
     }
     const unsigned bid = blockIdx.x - a.nb_lin;
@@ -2233,8 +2241,8 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     const int split = li >= 2 && nbits <= 56;
     const int hb = li / 2, lb = li - hb;
     const uint64_t nh = (uint64_t)1 << hb, nl = (uint64_t)1 << lb;
-    // split: packed H and L of the five points, then as lazy limbs H, H folded once, L
-    const uint64_t split_words = 5 * (nh + nl) * 8 + 5 * (nh + (nh + 1) / 2 + nl) * 9;
+    // split: packed H and L of the five points, then as lazy limbs H, two buffers for the folded H, L
+    const uint64_t split_words = 5 * (nh + nl) * 8 + 5 * (nh + 2 * ((nh + 1) / 2) + nl) * 9;
     void* beta_mem = zk_alloc(ctx, split ? split_words * 4 : (uint64_t)5 * D * 32);
     // column sums handed from round to round (from round 1 on): two sets of three tables; a round
     // with c chunks of m pairs leaves c m entries, and chunks appear only below the fill threshold
@@ -2269,9 +2277,10 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     uint32_t* aux = base;
     ZkBeta8 beta8;
     for (int k = 0; k < 5; ++k) beta8.t[k] = make_tab((uint32_t*)beta_mem + (uint64_t)k * 8 * D, D);
-    SplitEq sp0 = {}, sp1 = {};   // as built (H scaled after the weights are drawn); H with v0 bound
+    SplitEq sp0 = {}, sp1 = {}, sp2 = {};   // as built (H scaled after the weights are drawn); H with the challenges
+                                            // bound so far, in turns
     SplitConvArgs sca = {};
-    sp0.lb = sp1.lb = lb;
+    sp0.lb = sp1.lb = sp2.lb = lb;
     if (split) {
         uint32_t* q = (uint32_t*)beta_mem;
         for (int k = 0; k < 5; ++k) {
@@ -2296,10 +2305,16 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
             q += 9 * ((nh + 1) / 2);
         }
         for (int k = 0; k < 5; ++k) {
+            sp2.H[k].p = q;
+            sp2.H[k].ps = (nh + 1) / 2;
+            q += 9 * ((nh + 1) / 2);
+        }
+        for (int k = 0; k < 5; ++k) {
             sp0.L[k].p = q;
             sp0.L[k].ps = nl;
             q += 9 * nl;
             sp1.L[k] = sp0.L[k];
+            sp2.L[k] = sp0.L[k];
             sca.dst[5 + k] = sp0.L[k];
         }
     }
@@ -2370,6 +2385,13 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         hipLaunchKernelGGL(k_zk_scale, dim3(blocks_for(D, 65536)), dim3(ZK_BLOCK), 0, ctx->stream, beta8, tabs, D,
                            (const Fr*)st->weights, has_ga);
 
+    // Rounds that take the equality tables from their two factors: 0 and 1, and further rounds
+    // while their variable lies in H and the round is large (its linear part is bound by the
+    // table traffic then); the last of them writes the folded tables for the rounds after it.
+    int sp_rounds = split ? 2 : 0;
+    if (split)
+        while (sp_rounds < hb && sp_rounds < li && (D >> (sp_rounds + 1)) >= 2 * fill_threads) ++sp_rounds;
+
     BinArgs ba;
     ba.z = z_dev;
     ba.ga = ga_dev;
@@ -2405,11 +2427,14 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         ra.lin.ga = ga_dev;
         ra.lin.nbits = nbits;
         ra.lin.r_bits = R;
-        ra.lin.sp = t == 0 ? sp0 : sp1;
-        ba.split = split && t <= 1;
-        ba.sH = t == 0 ? sp0.H[4] : sp1.H[4];
+        const SplitEq& sp_t = t == 0 ? sp0 : (t & 1) ? sp1 : sp2;
+        ra.lin.sp = sp_t;
+        ra.lin.split_eq = t < sp_rounds;
+        ra.lin.write_eq = t + 1 == sp_rounds;
+        ba.split = t < sp_rounds;
+        ba.sH = sp_t.H[4];
         // few pairs: 16 per block, spread over (table, pair) and (point, equation, pair) threads
-        ra.lin_small = !ra.lin.from_ints && m <= (uint64_t)LIN_SMALL_PAIRS * (ZK_MAX_PART_BLOCKS / 2);
+        ra.lin_small = !ra.lin.from_ints && !ra.lin.split_eq && m <= (uint64_t)LIN_SMALL_PAIRS * (ZK_MAX_PART_BLOCKS / 2);
         const unsigned n_eq = has_ga ? 4 : 2;
         ra.lin.eq_blocks = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / n_eq);
         const unsigned nb_lin = ra.lin.from_ints && t == 0 ? n_eq * ra.lin.eq_blocks
@@ -2472,9 +2497,11 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         zk_prof_end(ctx);
         // g(1) is taken from the running claim: the binarity kernels leave it out
         zk_launch_finalise(ctx, (int)(nb_lin + nb_bin), 4, c_v + t, rounds_off + (uint32_t)t * 128, 0, 0, 1);
-        if (split && t == 0)   // round 1 reads the H factors with v0 bound
-            hipLaunchKernelGGL(k_zk_split_fold, dim3(blocks_for(nh / 2, 64), 5), dim3(ZK_BLOCK), 0, ctx->stream, sp0, sp1,
-                               nh / 2, (const Fr*)&st->chal[c_v], has_ga);
+        if (t + 1 < sp_rounds && (nh >> (t + 1)) >= 1) {   // the next round reads the H factors with v_t bound
+            const SplitEq& sp_n = ((t + 1) & 1) ? sp1 : sp2;
+            hipLaunchKernelGGL(k_zk_split_fold, dim3(blocks_for(nh >> (t + 1), 64), 5), dim3(ZK_BLOCK), 0, ctx->stream,
+                               sp_t, sp_n, nh >> (t + 1), (const Fr*)&st->chal[c_v + t], has_ga);
+        }
         if (t + 1 == mat_bound) {
             // bind the first challenges: bits -> field elements, one look-up per entry
             int jc = nbits;
