@@ -91,7 +91,9 @@ int zkdl_ctx_destroy(zkdl_ctx* ctx);
 int zkdl_last_hip_error(const zkdl_ctx* ctx);
 /* Tuning: zkrelu_prove cuts the bit columns of a round into chunks (more threads per row pair)
  * until about `threads` threads are busy; the default, 65536, is one wave on every SIMD of the
- * device.  Proofs do not depend on it.  1 <= threads <= 2^24, else ZKDL_EINVAL. */
+ * device.  The same figure decides from which size on the later rounds of its linear equations keep the
+ * equality tables as two factors and round 4 of the binarity sum runs on the integers.  Proofs do not
+ * depend on it.  1 <= threads <= 2^24, else ZKDL_EINVAL. */
 int zkdl_ctx_set_fill_threads(zkdl_ctx* ctx, uint64_t threads);
 const char* zkdl_strerror(int err);
 /* Frees cached scratch memory (the context keeps freed blocks for reuse). */

@@ -576,8 +576,16 @@ __device__ __forceinline__ F9 fold_ints(const F9* k, int64_t a0, int64_t a2) {
 }
 
 // Round 1: v0 is bound on the way; the equality tables come from their two factors (H already
-// folded), the value tables from the integers; both are written out folded (length 2m).
-__device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned bx, const unsigned gx) {
+// folded), the value tables from the integers and are written out folded (length 2m).  As in
+// round 0 a block takes one equation and a contiguous range of pair indices, and the sums are
+// grouped by the H index: with b = (bh, bl) and u = L[bl] value,
+//   "in" equations:  sum_b beta(x, b) q_b(x)        = sum_bh Hline_bh(x) line(sum u_lo, sum u_hi)(x),
+//   "out" equations: sum_b beta(x, b) ns_b(x) q_b(x) = sum_bh Hline_bh(x) sum ns_b(x) line(u_lo, u_hi)(x),
+// so a pair costs two products (five with the factor 1 - sign) next to the two folds of its value
+// table, and the line of H is multiplied in once per run.  Equation 1 also writes the folded
+// 1 - sign table; the folded equality tables are written only if the next round reads them from
+// memory (write_eq).
+__device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned bx) {
     __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
     __shared__ F9 kf[4];     // R^2, -R^2, v0 R^2, -v0 R^2
     __shared__ F9 kns[4];    // 1 - sign folded, by (bit at x0 = 0) + 2 (bit at x0 = 1): 0, 1 - v0, v0, 1
@@ -589,68 +597,112 @@ __device__ __forceinline__ void lin1_int_body(const LinArgs& a, const unsigned b
                                      : threadIdx.x == 2 ? v0 : one);
     }
     __syncthreads();
-    F9 acc[3];
-#pragma unroll
-    for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
+    const unsigned nbq = a.eq_blocks, e = bx / nbq, q = bx % nbq;
+    const bool with_ns = e & 1;
     const uint64_t m = a.m;
-    for (uint64_t b = bx * (uint64_t)blockDim.x + threadIdx.x; b < m; b += (uint64_t)gx * blockDim.x) {
-        F9 lo, hi, ns[3], p[3], q[3];
+    const int lb = a.sp.lb;
+    const uint64_t hh = m >> lb;                  // H entries per half; 0 (D < 16): the pair differs inside L
+    const uint64_t per = ((m + nbq - 1) / nbq + ZK_BLOCK - 1) / ZK_BLOCK * ZK_BLOCK;
+    const uint64_t b0 = q * per, b1 = b0 + per < m ? b0 + per : m;
+    const F9Tab H = a.sp.H[e], L = a.sp.L[e];
+    const F9Tab vt = a.tabs.t[e == 0 ? T_Z : e == 1 ? T_ZP : e == 2 ? T_GA : T_GAP];
+    const F9Tab et = a.tabs.t[e == 0 ? T_BZ : e == 1 ? T_BA : e == 2 ? T_BGA : T_BGZ];
+    F9 acc[3], tot[3];   // acc: "in": sums of u_lo, u_hi (third unused); "out": sums at x = 0, 2, 3
+#pragma unroll
+    for (int x = 0; x < 3; ++x) acc[x] = tot[x] = f9_zero();
+    const uint64_t none = ~(uint64_t)0;
+    uint64_t cur = none;
+    auto flush = [&](uint64_t bh) {
+        F9 hl[3], s[3];
+        line3<true>(f9tab_ld(H, bh), f9tab_ld(H, bh + hh), hl);
+        if (with_ns) {
+#pragma unroll
+            for (int x = 0; x < 3; ++x) s[x] = acc[x];
+        } else {
+            line3<true>(acc[0], acc[1], s);
+        }
+#pragma unroll
+        for (int x = 0; x < 3; ++x) {
+            tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(hl[x], s[x])));
+            acc[x] = f9_zero();
+        }
+    };
+    for (uint64_t b = b0 + threadIdx.x; b < b1; b += ZK_BLOCK) {
+        const uint64_t bh = b >> lb;
+        if (hh != 0 && bh != cur) {
+            if (cur != none) flush(cur);
+            cur = bh;
+        }
         IntRow r[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) r[i] = int_row(a.z[b + i * m], a.nbits, a.r_bits);
-        // rows b, b + 2m fold into lo; b + m, b + 3m into hi
-        lo = kns[(int)(r[0].ns + 2 * r[2].ns)];
-        hi = kns[(int)(r[1].ns + 2 * r[3].ns)];
-        f9tab_st(a.tabs.t[T_NS], b, lo);
-        f9tab_st(a.tabs.t[T_NS], b + m, hi);
-        line3<false>(lo, hi, ns);
-        eq_pair<true, true>(a, 0, T_BZ, b, m, kf[0], lo, hi);
-        line3<true>(lo, hi, p);
-        lo = fold_ints(kf, r[0].z, r[2].z);
-        hi = fold_ints(kf, r[1].z, r[3].z);
-        f9tab_st(a.tabs.t[T_Z], b, lo);
-        f9tab_st(a.tabs.t[T_Z], b + m, hi);
-        line3<false>(lo, hi, q);
+        int64_t v4[4];   // the value rows: b, b + 2m fold into lo; b + m, b + 3m into hi
 #pragma unroll
-        for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
-        eq_pair<true, true>(a, 1, T_BA, b, m, kf[0], lo, hi);
-        line3<true>(lo, hi, p);
-        lo = fold_ints(kf, r[0].zp, r[2].zp);
-        hi = fold_ints(kf, r[1].zp, r[3].zp);
-        f9tab_st(a.tabs.t[T_ZP], b, lo);
-        f9tab_st(a.tabs.t[T_ZP], b + m, hi);
-        line3<false>(lo, hi, q);
+        for (int i = 0; i < 4; ++i) {
+            if (e < 2) {
+                v4[i] = e == 0 ? r[i].z : r[i].zp;
+            } else {
+                const int64_t g = a.ga[b + i * m];
+                v4[i] = e == 2 ? g : rescale_half_up(g, a.r_bits);
+            }
+        }
+        const F9 lo = fold_ints(kf, v4[0], v4[2]), hi = fold_ints(kf, v4[1], v4[3]);
+        f9tab_st(vt, b, lo);
+        f9tab_st(vt, b + m, hi);
+        const uint64_t mask = ((uint64_t)1 << lb) - 1;
+        const F9 llo = f9tab_ld(L, b & mask), lhi = hh ? llo : f9tab_ld(L, (b + m) & mask);
+        if (hh == 0) {
+            // D < 16: the pair differs inside L, so the equality line is not a multiple of one L
+            // entry; each pair is worked out by itself (cur stays unset: nothing to flush)
+            const F9 h0 = f9tab_ld(H, 0);
+            const F9 plo = f9_mul(h0, llo), phi = f9_mul(h0, lhi);
+            if (a.write_eq) {
+                f9tab_st(et, b, plo);
+                f9tab_st(et, b + m, phi);
+            }
+            F9 p[3], qv[3];
+            line3<true>(plo, phi, p);
+            line3<false>(lo, hi, qv);
+            if (with_ns) {
+                const F9 nlo = kns[(int)(r[0].ns + 2 * r[2].ns)], nhi = kns[(int)(r[1].ns + 2 * r[3].ns)];
+                if (e == 1) {
+                    f9tab_st(a.tabs.t[T_NS], b, nlo);
+                    f9tab_st(a.tabs.t[T_NS], b + m, nhi);
+                }
+                F9 ns[3];
+                line3<false>(nlo, nhi, ns);
 #pragma unroll
-        for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(f9_mul(p[x], ns[x]), q[x]));
+                for (int x = 0; x < 3; ++x) tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(f9_mul(p[x], ns[x]), qv[x])));
+            } else {
 #pragma unroll
-        for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
-        if (a.has_ga) {
+                for (int x = 0; x < 3; ++x) tot[x] = f9_norm_reduce(f9_add(tot[x], f9_mul(p[x], qv[x])));
+            }
+            continue;
+        }
+        const F9 ulo = f9_mul(llo, lo), uhi = f9_mul(lhi, hi);     // normal, below 2 r
+        if (a.write_eq) {
+            f9tab_st(et, b, f9_mul(f9tab_ld(H, bh), llo));
+            f9tab_st(et, b + m, f9_mul(f9tab_ld(H, bh + hh), lhi));
+        }
+        if (with_ns) {
+            const F9 nlo = kns[(int)(r[0].ns + 2 * r[2].ns)], nhi = kns[(int)(r[1].ns + 2 * r[3].ns)];
+            if (e == 1) {
+                f9tab_st(a.tabs.t[T_NS], b, nlo);
+                f9tab_st(a.tabs.t[T_NS], b + m, nhi);
+            }
+            F9 ns[3], uq[3];
+            line3<false>(nlo, nhi, ns);
+            line3<true>(ulo, uhi, uq);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) r[i] = int_row(a.ga[b + i * m], a.nbits, a.r_bits);
-            eq_pair<true, true>(a, 2, T_BGA, b, m, kf[0], lo, hi);
-            line3<true>(lo, hi, p);
-            lo = fold_ints(kf, r[0].z, r[2].z);
-            hi = fold_ints(kf, r[1].z, r[3].z);
-            f9tab_st(a.tabs.t[T_GA], b, lo);
-            f9tab_st(a.tabs.t[T_GA], b + m, hi);
-            line3<false>(lo, hi, q);
-#pragma unroll
-            for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(p[x], q[x]));
-            eq_pair<true, true>(a, 3, T_BGZ, b, m, kf[0], lo, hi);
-            line3<true>(lo, hi, p);
-            lo = fold_ints(kf, r[0].zp, r[2].zp);
-            hi = fold_ints(kf, r[1].zp, r[3].zp);
-            f9tab_st(a.tabs.t[T_GAP], b, lo);
-            f9tab_st(a.tabs.t[T_GAP], b + m, hi);
-            line3<false>(lo, hi, q);
-#pragma unroll
-            for (int x = 0; x < 3; ++x) acc[x] = f9_add(acc[x], f9_mul(f9_mul(p[x], ns[x]), q[x]));
-#pragma unroll
-            for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
+            for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(f9_add(acc[x], f9_mul(uq[x], ns[x])));
+        } else {
+            acc[0] = f9_norm_reduce(f9_add(acc[0], ulo));
+            acc[1] = f9_norm_reduce(f9_add(acc[1], uhi));
         }
     }
+    if (cur != none) flush(cur);
     {
-        const Fr s = block_sum_lazy<3>(acc, red);
+        const Fr s = block_sum_lazy<3>(tot, red);
         Fr* pp = a.part + (uint64_t)bx * 4;
         if (threadIdx.x < 3) pp[threadIdx.x ? threadIdx.x + 1 : 0] = s;
         else if (threadIdx.x == 3) pp[1] = fr_zero();
@@ -1859,7 +1911,7 @@ __global__ __launch_bounds__(ZK_BLOCK, 2) void k_zk_round(ZkRoundArgs a) {
     if (blockIdx.x < a.nb_lin) {
         if (MODE <= 1 && a.lin.from_ints) {
             if (MODE == 0) lin0_int_body(a.lin, blockIdx.x);
-            else lin1_int_body(a.lin, blockIdx.x, a.nb_lin);
+            else lin1_int_body(a.lin, blockIdx.x);
         } else if (MODE >= 2 && a.lin.split_eq) lin_body<true, true>(a.lin, blockIdx.x, a.nb_lin);
         else if (a.lin_small) lin_body_small<MODE != 0>(a.lin, blockIdx.x);
         else lin_body<MODE != 0, false>(a.lin, blockIdx.x, a.nb_lin);
@@ -2437,7 +2489,7 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
         ra.lin_small = !ra.lin.from_ints && !ra.lin.split_eq && m <= (uint64_t)LIN_SMALL_PAIRS * (ZK_MAX_PART_BLOCKS / 2);
         const unsigned n_eq = has_ga ? 4 : 2;
         ra.lin.eq_blocks = blocks_for(m, ZK_MAX_PART_BLOCKS / 2 / n_eq);
-        const unsigned nb_lin = ra.lin.from_ints && t == 0 ? n_eq * ra.lin.eq_blocks
+        const unsigned nb_lin = ra.lin.from_ints ? n_eq * ra.lin.eq_blocks
                                 : ra.lin_small       ? (unsigned)((m + LIN_SMALL_PAIRS - 1) / LIN_SMALL_PAIRS)
                                                      : blocks_for(m, ZK_MAX_PART_BLOCKS / 2);
         ra.nb_lin = nb_lin;
