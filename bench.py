@@ -3,8 +3,13 @@
 A step is one pass of the kernel micro-benchmark workload: a degree-3 sumcheck
 over the product of three tables of 2^24 uniform Fr elements (24 rounds) plus
 the partial evaluation of a 4096 x 4096 uniform Fr matrix at a random row point.
-Inputs are resident in HBM before the timed region.  Prints one JSON line; the
-fields are described in the design doc.
+Inputs are resident in HBM before the timed region.  Prints one JSON line:
+`value` = Fr elements through the step per second; `config` names the workload and carries the
+median times of its two parts, of the one-layer proofs and of the aggregated proofs of the
+8 x 1024^2 (batch 64; one step and 16 steps) and 4 x 4096^2 (batch 256) networks; `roofline` =
+algorithmic bytes of the fused round kernels over their launch time measured with HIP events on
+the library's stream (plus the multiply-add rate and the other kernel classes); `cpu_baseline` =
+the CPU oracle's rate on the host cores.
 """
 import argparse
 import json
