@@ -343,6 +343,33 @@ def test_zkrelu_column_chunking(lib, fill, d_len, with_ga):
     c2.close()
 
 
+@pytest.mark.parametrize("d_len,with_ga", [(1 << 16, True), (1 << 18, False)])
+def test_zkrelu_paths_agree_at_larger_sizes(lib, d_len, with_ga):
+    """At sizes the Python oracle cannot prove in reasonable time: every way of cutting the work
+    (whole columns per thread with round 4 on the integers and split equality tables in all
+    large rounds, a few chunks, the default) gives the same proof, and the oracle's verifier
+    accepts it and ends in the same transcript state."""
+    import paper_2307_16273_amd as zk
+    rng = np.random.default_rng(d_len)
+    lim = 1 << 47
+    z = rng.integers(-lim, lim, d_len, dtype=np.int64)
+    ga = rng.integers(-lim, lim, d_len, dtype=np.int64) if with_ga else None
+    proofs = []
+    for fill in (1, 2048, 65536):
+        say(f"zkrelu D={d_len} ga={with_ga} fill_threads={fill}")
+        c2 = zk.Context(0)
+        c2.set_fill_threads(fill)
+        tr = lib.Transcript(24)
+        got = lib.zkrelu_prove(c2, z, ga, tr, 32, 16)
+        proofs.append((got["proof"], got["points"], tr.digest()))
+        c2.close()
+    assert proofs[0] == proofs[1] == proofs[2]
+    ots = OracleTranscript(24)
+    P.zkrelu_verify(proofs[0][0], ots)
+    assert ots.digest() == proofs[0][2]
+    assert ots.challenges == proofs[0][1]
+
+
 @pytest.mark.parametrize("q,r", [(40, 16), (32, 16), (55, 1)])
 def test_zkrelu_extreme_values(lib, ctx, q, r):
     """Every entry at an end of the (Q+R)-bit range, arranged so that the pairs and quadruples
