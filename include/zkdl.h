@@ -224,6 +224,18 @@ int zkrelu_prove(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint64_t D,
                  int src_on_device, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
                  zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints);
 
+/* zkrelu_prove_at: the same proof with the four points of the input claims given by the
+ * caller instead of drawn (Sec. 3.2, App. A: they are the points that the sumchecks of the
+ * operations Z, A, G_A, G_Z take part in have left).  points (host): 4 log2 D canonical
+ * elements, u_Z, u_A, u_GA, u_GZ in this order, each with the most significant index bit
+ * first; may be NULL only if D = 1.  Transcript: header "zkrelu_at" (log2 D, Q, R, has_GA,
+ * 1), then "u" with the SHA-256 digest of the 4 log2 D x 32 point bytes; only u_bin is
+ * drawn; from the claims on as zkrelu_prove.  Word 5 of the proof header is 1.  points_out
+ * starts with the four given points.  ZKDL_EINVAL for a coordinate that is not below r. */
+int zkrelu_prove_at(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint64_t D, int Q, int R,
+                    int src_on_device, const zkdl_fr* points, zkdl_transcript* tr, uint8_t* proof,
+                    size_t* proof_len, zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints);
+
 /* One aggregation window of an L-layer width x width FCNN (Example FCNN,
  * Protocol zkdl): T' steps, stack slot n = t L + (l-1), N = T' L.  All five
  * stacks are device memory, row-major:

@@ -369,7 +369,32 @@ def _merge_tables(m_table, wbar, rho, b, lj):
     return [np.asarray(m_table, dtype=object).reshape(-1), e]
 
 
-def zkrelu_prove(z, ga, q, r_bits, ts):
+def _points_digest(points):
+    """SHA-256 of the four points u_Z, u_A, u_GA, u_GZ, 32 B little-endian per coordinate."""
+    import hashlib
+    return hashlib.sha256(b"".join(to_le(x) for pt in points for x in pt)).digest()
+
+
+def _zkrelu_points(ts, li, lj, q, r_bits, has_ga, points, bind_points):
+    """Header and the five points.  points=None: all five drawn (one draw).  Otherwise the
+    four points of the input claims are the caller's (Sec. 3.2 and App. A: they are left by
+    the sumchecks of the operations the four tensors take part in) and only u_bin is drawn;
+    with bind_points they are bound through their digest (a call on its own), without it
+    they must be functions of this transcript already (a call inside a larger proof)."""
+    if points is None:
+        ts.absorb_u32(b"zkrelu", [li, q, r_bits, 1 if has_ga else 0])
+        pt = ts.challenges_vec(5 * li + lj)
+        return pt[:li], pt[li:2 * li], pt[2 * li:3 * li], pt[3 * li:4 * li], pt[4 * li:], 0
+    assert len(points) == 4 and all(len(pt) == li for pt in points)
+    mode = 1 if bind_points else 2
+    ts.absorb_u32(b"zkrelu_at", [li, q, r_bits, 1 if has_ga else 0, mode])
+    if bind_points:
+        ts.absorb(b"u", _points_digest(points))
+    u_bin = ts.challenges_vec(li + lj)
+    return [list(pt) for pt in points] + [u_bin, mode]
+
+
+def zkrelu_prove(z, ga, q, r_bits, ts, points=None, bind_points=True):
     """Combined zkReLU sumcheck (App. A) followed by the merge of the three
     claims on aux into one.
 
@@ -378,7 +403,9 @@ def zkrelu_prove(z, ga, q, r_bits, ts):
     Transcript order: header; u_Z, u_A, u_GA, u_GZ (log D each), u_bin
     (log D + log J); absorb the four input claims; r, r'; rounds; finals
     (aux~(0,v,wbar), aux~(1,v,wbar), aux~(0,v,Q+R-1)); rho0..2; merge rounds;
-    merge finals (aux~(k*,v,w*), E~(k*,w*))."""
+    merge finals (aux~(k*,v,w*), E~(k*,w*)).
+    `points` = (u_Z, u_A, u_GA, u_GZ) replaces the draw of these four (see _zkrelu_points);
+    word 5 of the proof header then holds the mode (1 bound by digest, 2 unbound)."""
     d_len = len(z)
     has_ga = ga is not None
     if ga is None:
@@ -388,10 +415,7 @@ def zkrelu_prove(z, ga, q, r_bits, ts):
     j_pad = wit["j_pad"]
     li, lj = ilog2(d_len), ilog2(j_pad)
     b = q + r_bits
-    ts.absorb_u32(b"zkrelu", [li, q, r_bits, 1 if has_ga else 0])
-    pt = ts.challenges_vec(5 * li + lj)           # all five points: one draw
-    u_z, u_a, u_ga, u_gz, u_bin = (pt[:li], pt[li:2 * li], pt[2 * li:3 * li], pt[3 * li:4 * li],
-                                   pt[4 * li:])
+    u_z, u_a, u_ga, u_gz, u_bin, mode = _zkrelu_points(ts, li, lj, q, r_bits, has_ga, points, bind_points)
     c_in = [mle_eval(fr_array(wit["Z"]), u_z), mle_eval(fr_array(wit["A"]), u_a),
             mle_eval(fr_array(wit["GA"]), u_ga), mle_eval(fr_array(wit["GZ"]), u_gz)]
     ts.absorb_fr(b"c", c_in)
@@ -441,19 +465,21 @@ def zkrelu_prove(z, ga, q, r_bits, ts):
                       absorb_claim=False)
     assert merge.claim0 == sum(x * y for x, y in zip(rho, proof.finals)) % R_MOD
 
-    head = struct.pack("<IIIIIIII", ZKRL_MAGIC, li, q, r_bits, 1 if has_ga else 0, 0, 0, 0)
+    head = struct.pack("<IIIIIIII", ZKRL_MAGIC, li, q, r_bits, 1 if has_ga else 0, mode, 0, 0)
     buf = head + b"".join(to_le(c) for c in c_in) + proof.to_bytes() + merge.to_bytes()
     info = dict(u_z=u_z, u_a=u_a, u_ga=u_ga, u_gz=u_gz, u_bin=u_bin, c_in=c_in, r=r, rp=rp,
                 v=vs, rho=rho, vm=vm, proof=proof, merge=merge, wit=wit)
     return buf, info
 
 
-def zkrelu_verify(buf, ts, off=0):
+def zkrelu_verify(buf, ts, off=0, points=None):
     """Replay a zkReLU proof.  Checks every round, the final combined claim and
     the merge; the one remaining claim on aux, (k*, v, w*) -> value, is returned
-    for the (out-of-scope) proof of evaluation."""
-    magic, li, q, r_bits, has_ga, _, _, _ = struct.unpack_from("<IIIIIIII", buf, off)
+    for the (out-of-scope) proof of evaluation.  `points`: the verifier's own copy of the
+    four points when the proof was made at given points (header mode 1 or 2)."""
+    magic, li, q, r_bits, has_ga, mode, _, _ = struct.unpack_from("<IIIIIIII", buf, off)
     assert magic == ZKRL_MAGIC
+    assert (mode == 0) == (points is None), "proof mode and the verifier's points disagree"
     off += 32
     c_in = [from_le(buf[off + 32 * k: off + 32 * k + 32]) for k in range(4)]
     off += 128
@@ -464,10 +490,7 @@ def zkrelu_verify(buf, ts, off=0):
     b = q + r_bits
     assert proof.degree == 3 and len(proof.rounds) == li + lj and proof.n_finals == 3
     assert merge.degree == 2 and len(merge.rounds) == 1 + lj and merge.n_finals == 2
-    ts.absorb_u32(b"zkrelu", [li, q, r_bits, has_ga])
-    pt = ts.challenges_vec(5 * li + lj)           # all five points: one draw
-    u_z, u_a, u_ga, u_gz, u_bin = (pt[:li], pt[li:2 * li], pt[2 * li:3 * li], pt[3 * li:4 * li],
-                                   pt[4 * li:])
+    u_z, u_a, u_ga, u_gz, u_bin, _ = _zkrelu_points(ts, li, lj, q, r_bits, has_ga, points, mode == 1)
     ts.absorb_fr(b"c", c_in)
     r, rp = ts.challenges_vec(2)
     r2 = r * r % R_MOD

@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = [
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
     "mle_partial_eval", "sumcheck_product", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_hadamard",
-    "reindex_prove", "zkrelu_prove", "aggregate_prove", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
+    "reindex_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read",
 ]
 
@@ -74,6 +74,7 @@ def load_library():
         "sumcheck_hadamard": [vp, vp, vp, vp, vp, psz, vp, vp, psz],
         "reindex_prove": [vp, vp, i, pp, C.POINTER(u64), pp, vp, vp, vp, psz, vp, vp, psz],
         "zkrelu_prove": [vp, vp, vp, u64, i, i, i, vp, vp, psz, vp, vp, psz],
+        "zkrelu_prove_at": [vp, vp, vp, u64, i, i, i, vp, vp, vp, psz, vp, vp, psz],
         "aggregate_prove": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
         "zkdl_host_fr_mul": [vp, vp, vp], "zkdl_selfcheck_constants": [],
         "zkdl_ctx_profile_enable": [vp, i], "zkdl_ctx_profile_reset": [vp],
@@ -343,8 +344,10 @@ def reindex_prove(ctx, x, maps, points, u, tr):
     return o.result()
 
 
-def zkrelu_prove(ctx, z, ga, tr, q=32, r=16):
-    """z, ga: int64 numpy arrays (host) or int64 CUDA tensors; ga may be None."""
+def zkrelu_prove(ctx, z, ga, tr, q=32, r=16, points=None):
+    """z, ga: int64 numpy arrays (host) or int64 CUDA tensors; ga may be None.
+    points: None, or the four points (u_Z, u_A, u_GA, u_GZ) as lists of field elements
+    (zkrelu_prove_at)."""
     zp, z_dev, zc, zk_ = _src_pointer(z)
     assert zc == ZKDL_I64
     d = int(np.prod(z.shape))
@@ -353,6 +356,14 @@ def zkrelu_prove(ctx, z, ga, tr, q=32, r=16):
         gp, g_dev, gc, gk_ = _src_pointer(ga)
         assert gc == ZKDL_I64 and g_dev == z_dev
     o = _Outputs(4)
+    if points is not None:
+        assert len(points) == 4
+        flat = [x for pt in points for x in pt]
+        pb = C.create_string_buffer(_fr_bytes(flat), max(32 * len(flat), 1))
+        _check(load_library().zkrelu_prove_at(ctx.handle, zp, gp, d, q, r, z_dev, pb, tr.handle, o.proof,
+                                              C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
+               "zkrelu_prove_at", ctx)
+        return o.result()
     _check(load_library().zkrelu_prove(ctx.handle, zp, gp, d, q, r, z_dev, tr.handle, o.proof,
                                        C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
            "zkrelu_prove", ctx)

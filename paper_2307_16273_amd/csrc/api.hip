@@ -1039,24 +1039,59 @@ static int stage_ints(zkdl_ctx* ctx, const int64_t* host, uint64_t n, void** dev
 static const uint32_t ZKRL_MAGIC = 0x4C524B5Au;
 static const uint32_t ZKAG_MAGIC = 0x47414B5Au;
 
+// mode 0: all five points drawn.  mode 1 / 2: the four points of the input claims stand in
+// chal[n_chal ..) already; 1 binds them through `digest` (8 words), 2 does not (they are
+// functions of this transcript).
 static int enqueue_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q,
-                          int R) {
+                          int R, int mode, const uint32_t* digest) {
     if (!is_pow2(D) || Q < 1 || R < 1 || Q + R > 64 || Q + R < 2) return ZKDL_EINVAL;
-    uint32_t hw[4] = {(uint32_t)ilog2_u64(D), (uint32_t)Q, (uint32_t)R, ga_dev ? 1u : 0u};
-    zk_absorb_words(ctx, "zkrelu", hw, 4);
-    uint32_t hdr[8] = {ZKRL_MAGIC, hw[0], hw[1], hw[2], hw[3], 0, 0, 0};
+    uint32_t hw[5] = {(uint32_t)ilog2_u64(D), (uint32_t)Q, (uint32_t)R, ga_dev ? 1u : 0u, (uint32_t)mode};
+    if (mode == 0) {
+        zk_absorb_words(ctx, "zkrelu", hw, 4);
+    } else {
+        zk_absorb_words(ctx, "zkrelu_at", hw, 5);
+        if (mode == 1) zk_absorb_words(ctx, "u", digest, 8);
+    }
+    uint32_t hdr[8] = {ZKRL_MAGIC, hw[0], hw[1], hw[2], hw[3], hw[4], 0, 0};
     zk_write_proof_words(ctx, hdr, 8);
-    return zk_zkrelu(ctx, z_dev, ga_dev, D, Q, R);
+    return zk_zkrelu(ctx, z_dev, ga_dev, D, Q, R, mode != 0);
 }
 
-extern "C" int zkrelu_prove(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint64_t D, int Q, int R,
-                            int src_on_device, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
-                            zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {
+// 32 little-endian bytes below the modulus
+static bool fr_bytes_canonical(const uint8_t* le) {
+    for (int l = 7; l >= 0; --l) {
+        const uint32_t w = (uint32_t)le[4 * l] | ((uint32_t)le[4 * l + 1] << 8) | ((uint32_t)le[4 * l + 2] << 16) |
+                           ((uint32_t)le[4 * l + 3] << 24);
+        if (w != frc::MOD[l]) return w < frc::MOD[l];
+    }
+    return false;
+}
+
+static int zkrelu_call(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint64_t D, int Q, int R,
+                       int src_on_device, const zkdl_fr* points, zkdl_transcript* tr, uint8_t* proof,
+                       size_t* proof_len, zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {
     if (!ctx || !Z || !tr) return ZKDL_EINVAL;
     if (!is_pow2(D) || D > ((uint64_t)1 << 30)) return ZKDL_EINVAL;
+    const int li = ilog2_u64(D);
     int rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
-    void *zs = nullptr, *gs = nullptr;
+    void *zs = nullptr, *gs = nullptr, *d_pts = nullptr;
+    uint32_t dgw[8] = {};
+    if (points) {
+        // the four points, in the order u_Z, u_A, u_GA, u_GZ: hashed, and placed where the
+        // drawn ones would stand
+        HostSha hs;
+        hs.bytes(points, (size_t)4 * li * 32);
+        uint8_t dg[32];
+        ts::digest(hs.s, dg);
+        for (int i = 0; i < 8; ++i)
+            dgw[i] = (uint32_t)dg[4 * i] | ((uint32_t)dg[4 * i + 1] << 8) | ((uint32_t)dg[4 * i + 2] << 16) |
+                     ((uint32_t)dg[4 * i + 3] << 24);
+        if (li > 0) {
+            rc = upload_bytes(ctx, points, (size_t)4 * li * 32, &d_pts);
+            if (rc == ZKDL_OK) zk_launch_chal_set(ctx, ctx->n_chal, 4 * li, (const uint8_t*)d_pts, nullptr);
+        }
+    }
     const int64_t* zd = Z;
     const int64_t* gd = GA;
     if (!src_on_device) {
@@ -1067,12 +1102,32 @@ extern "C" int zkrelu_prove(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, 
             gd = (const int64_t*)gs;
         }
     }
-    if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, zd, gd, D, Q, R);
+    if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, zd, gd, D, Q, R, points ? 1 : 0, dgw);
     int ids[4] = {0, 1, 2, 3};
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 4, claims);
     zk_free(ctx, zs);
     zk_free(ctx, gs);
+    zk_free(ctx, d_pts);
     return rc != ZKDL_OK ? rc : rc2;
+}
+
+extern "C" int zkrelu_prove(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint64_t D, int Q, int R,
+                            int src_on_device, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+                            zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {
+    return zkrelu_call(ctx, Z, GA, D, Q, R, src_on_device, nullptr, tr, proof, proof_len, claims, points_out,
+                       npoints);
+}
+
+extern "C" int zkrelu_prove_at(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint64_t D, int Q, int R,
+                               int src_on_device, const zkdl_fr* points, zkdl_transcript* tr, uint8_t* proof,
+                               size_t* proof_len, zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {
+    if (!is_pow2(D) || (D > 1 && !points)) return ZKDL_EINVAL;
+    static const zkdl_fr none = {};
+    for (int i = 0; i < 4 * ilog2_u64(D); ++i)
+        if (!fr_bytes_canonical(points[i].le)) return ZKDL_EINVAL;
+    if (!points) points = &none;   // D = 1: no coordinates, the header still says "given"
+    return zkrelu_call(ctx, Z, GA, D, Q, R, src_on_device, points, tr, proof, proof_len, claims, points_out,
+                       npoints);
 }
 
 extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr,
@@ -1096,7 +1151,7 @@ extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_t
     if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tG, &tW, 0, 1, w->L, 12, nullptr);
     // gradW: G_W^(l) = A^(l-1)T G_Z^(l)
     if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tA, &tG, 1, 0, 0, 16, nullptr);
-    if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, w->Zr, w->GA, N * w->B * w->width, (int)w->Q, (int)w->R);
+    if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, w->Zr, w->GA, N * w->B * w->width, (int)w->Q, (int)w->R, 0, nullptr);
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
     return rc != ZKDL_OK ? rc : rc2;
 }

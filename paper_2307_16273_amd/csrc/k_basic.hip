@@ -80,6 +80,33 @@ void zk_launch_points_to_mont(zkdl_ctx* ctx, const uint8_t* le_dev, int n, Fr* o
                        (const uint32_t*)le_dev, n, out);
 }
 
+// chal[dst + i] (and its little-endian copy) = the i-th given coordinate: taken from canonical
+// little-endian bytes, or, with le == nullptr, a copy of chal[idx.v[i]]
+__global__ void k_chal_set(DevState* st, int dst, int n, const uint32_t* le, ChalIdx idx) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    Fr x, xm;
+    if (le) {
+#pragma unroll
+        for (int l = 0; l < 8; ++l) x.v[l] = le[8 * i + l];
+        xm = fr_to_mont(x);
+    } else {
+        xm = st->chal[idx.v[i]];
+        x = fr_from_mont(xm);
+    }
+    st->chal[dst + i] = xm;
+    uint32_t* out = (uint32_t*)(st->chal_le + 32 * (size_t)(dst + i));
+#pragma unroll
+    for (int l = 0; l < 8; ++l) out[l] = x.v[l];
+}
+
+void zk_launch_chal_set(zkdl_ctx* ctx, int dst, int n, const uint8_t* le_dev, const ChalIdx* idx) {
+    if (n <= 0) return;
+    ChalIdx none = {};
+    hipLaunchKernelGGL(k_chal_set, dim3((n + 63) / 64), dim3(64), 0, ctx->stream, ctx->dev, dst, n,
+                       (const uint32_t*)le_dev, idx ? *idx : none);
+}
+
 // ---------------------------------------------------------------------------
 // beta~(u, .): the multilinear extension of the equality indicator (Sec. 2.2),
 // beta~(u, b) = prod_k (u_k b_k + (1 - u_k)(1 - b_k)), u_0 <-> most significant bit.

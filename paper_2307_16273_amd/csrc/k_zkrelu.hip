@@ -2227,7 +2227,8 @@ const uint32_t SC_MAGIC = 0x43534B5Au;
 
 }  // namespace
 
-int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q, int R) {
+int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q, int R,
+              int given_points) {
     const int nbits = Q + R;
     const int li = log2u(D);
     int lj = 0;
@@ -2259,7 +2260,8 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
     if (ctx->proof_len > (size_t)ZK_PROOF_CAP) return ZKDL_ESMALL;
 
     DevState* st = ctx->dev;
-    zk_launch_draw(ctx, c0, 5 * li + lj);
+    if (given_points) zk_launch_draw(ctx, c_ubin, li + lj);
+    else zk_launch_draw(ctx, c0, 5 * li + lj);
 
     // memory: 10 D-sized tables, beta_J, aux columns (2 * nbits columns of 36 B entries; the rows
     // are written once four challenges are bound, D/16 of them; fewer challenges if D < 16)

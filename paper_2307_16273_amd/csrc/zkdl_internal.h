@@ -117,6 +117,13 @@ static inline FrTab tab_offset(const FrTab& t, uint64_t elems) {
 void zk_launch_convert(zkdl_ctx* ctx, const void* src, int kind_or_le, uint64_t n, FrTab out);
 void zk_launch_download(zkdl_ctx* ctx, FrTab in, uint64_t n, uint8_t* out_le_dev);
 void zk_launch_points_to_mont(zkdl_ctx* ctx, const uint8_t* le_dev, int n, Fr* out);
+// chal[dst .. dst + n) = given coordinates: canonical little-endian bytes on the device, or
+// (le_dev == nullptr) copies of chal[idx->v[i]]; n <= ZK_CHAL_SET_MAX
+constexpr int ZK_CHAL_SET_MAX = 128;
+struct ChalIdx {
+    int16_t v[ZK_CHAL_SET_MAX];
+};
+void zk_launch_chal_set(zkdl_ctx* ctx, int dst, int n, const uint8_t* le_dev, const ChalIdx* idx);
 // beta~(point, .) for the m challenges point[0..m) (device, Montgomery, AoS)
 int zk_build_beta(zkdl_ctx* ctx, const Fr* point, int m, FrTab out);
 // several tables with two launches in all (tables of more than 2^22 entries are built one by one)
@@ -165,7 +172,9 @@ int zk_reindex(zkdl_ctx* ctx, const ReindexJob& job, FrTab t, FrTab p, int ln, v
 // optimized aggregated matrix-product protocol: stack rounds with f_t, then the single-product sumcheck
 int zk_matmul_ft(zkdl_ctx* ctx, const FrTab* src, void* work_mem, int ln, int l2, const FrTab* wsuf, int w_idx,
                  int finals_scal_base);
-int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q, int R);
+// given_points != 0: u_Z, u_A, u_GA, u_GZ already stand in chal[n_chal .. n_chal + 4 log2 D); only u_bin is drawn
+int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q, int R,
+              int given_points);
 
 // ---- api.hip -----------------------------------------------------------------------
 void zk_write_proof_words(zkdl_ctx* ctx, const uint32_t* words, int n);   // appends a header

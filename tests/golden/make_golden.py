@@ -68,6 +68,19 @@ def zkrelu_case():
             "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
 
 
+def zkrelu_at_case():
+    """zkReLU at four given points (Sec. 3.2, App. A): the same inputs, points from a seeded generator."""
+    z = [77, -128, -1, 100]
+    ga = [-5, 127, 0, -64]
+    rng = np.random.default_rng(20230719)
+    pts = [[int(v) for v in fr_array_from_le(uniform_fr_limbs(rng, 2).tobytes(), 2)] for _ in range(4)]
+    ts = Transcript(12)
+    buf, info = P.zkrelu_prove(z, ga, 5, 3, ts, points=pts)
+    return {"protocol": "zkrelu_prove_at", "cite": "Sec. 3.2, App. A", "seed": 12, "Z": z, "GA": ga, "Q": 5, "R": 3,
+            "points": [[hex(v) for v in pt] for pt in pts],
+            "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
+
+
 def aggregate_case():
     """Aggregated window (Sec. 5, Example FCNN): L = 2 layers of width 4, batch 2, 2 steps."""
     wit = fcnn_window(2307162730 + 90, 2, 4, 2, 2)
@@ -98,7 +111,8 @@ def reindex_case():
 if __name__ == "__main__":
     for name, fn in (("product_k3_d3", product_case), ("matmul_n2_2x4x2", matmul_case),
                      ("matmul_ft_n2_2x4x2", matmul_ft_case),
-                     ("zkrelu_d4_q5_r3", zkrelu_case), ("aggregate_l2_w4_b2_t2", aggregate_case),
+                     ("zkrelu_d4_q5_r3", zkrelu_case), ("zkrelu_at_d4_q5_r3", zkrelu_at_case),
+                     ("aggregate_l2_w4_b2_t2", aggregate_case),
                      ("reindex_n4_d8_k2", reindex_case)):
         with open(os.path.join(HERE, name + ".json"), "w") as f:
             json.dump(fn(), f, indent=1)

@@ -30,6 +30,8 @@ def oracle_run(g):
         buf = P.matmul_ft_prove(fr_array(np.array(g["x0"])), g["x0_shape"], fr_array(np.array(g["x1"])), g["x1_shape"], ts)[0]
     elif g["protocol"] == "zkrelu_prove":
         buf = P.zkrelu_prove(g["Z"], g["GA"], g["Q"], g["R"], ts)[0]
+    elif g["protocol"] == "zkrelu_prove_at":
+        buf = P.zkrelu_prove(g["Z"], g["GA"], g["Q"], g["R"], ts, points=[[int(v, 16) for v in pt] for pt in g["points"]])[0]
     elif g["protocol"] == "reindex_prove":
         n, d = g["x_shape"]
         pts = [[int(v) for v in fr_array_from_le(bytes.fromhex(h), len(h) // 64)] for h in g["points_le_hex"]]
@@ -41,7 +43,7 @@ def oracle_run(g):
     return bytes(buf), ts
 
 
-NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "zkrelu_d4_q5_r3", "aggregate_l2_w4_b2_t2",
+NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "zkrelu_d4_q5_r3", "zkrelu_at_d4_q5_r3", "aggregate_l2_w4_b2_t2",
          "reindex_n4_d8_k2"]
 
 
@@ -61,6 +63,7 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
     g = load(name)
     print(f"[golden] {name}", flush=True)
     tr = lib.Transcript(g["seed"])
+    given = []          # points the caller supplies come back in front of the drawn ones
     if g["protocol"] == "sumcheck_product":
         tabs = [lib.fr_tensor_upload(ctx, bytes.fromhex(h), (8,)) for h in g["tables_le_hex"]]
         got = lib.sumcheck_product(ctx, tabs, tr)
@@ -76,6 +79,11 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
         got = lib.reindex_prove(ctx, x, g["maps"], pts, u, tr)
     elif g["protocol"] == "zkrelu_prove":
         got = lib.zkrelu_prove(ctx, np.array(g["Z"], dtype=np.int64), np.array(g["GA"], dtype=np.int64), tr, g["Q"], g["R"])
+    elif g["protocol"] == "zkrelu_prove_at":
+        pts = [[int(v, 16) for v in pt] for pt in g["points"]]
+        given = [hex(v) for pt in pts for v in pt]
+        got = lib.zkrelu_prove(ctx, np.array(g["Z"], dtype=np.int64), np.array(g["GA"], dtype=np.int64), tr, g["Q"], g["R"],
+                               points=pts)
     else:
         wit = fcnn_window(2307162730 + 90, 2, 4, 2, 2)
         dw = {k: wit[k] for k in ("L", "B", "width", "T", "Q", "R")}
@@ -83,5 +91,5 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
             dw[k] = torch.from_numpy(np.ascontiguousarray(wit[k])).cuda()
         got = lib.aggregate_prove(ctx, dw, tr)
     assert got["proof"].hex() == g["proof_hex"]
-    assert [hex(v) for v in got["points"]] == g["challenges"]
+    assert [hex(v) for v in got["points"]] == given + g["challenges"]
     assert tr.digest().hex() == g["digest_hex"]

@@ -320,6 +320,43 @@ def test_zkrelu(lib, ctx, d_len, with_ga, q, r):
     assert tr.digest() == ots.digest()
 
 
+@pytest.mark.parametrize("d_len,with_ga,q,r", [(1, True, 32, 16), (2, True, 32, 16), (8, False, 5, 3),
+                                               (64, True, 32, 16), (2048, True, 32, 16), (512, True, 48, 16)])
+def test_zkrelu_at_given_points(lib, ctx, d_len, with_ga, q, r):
+    """The four points of the input claims supplied by the caller (bound by their digest)."""
+    say(f"zkrelu_at D={d_len} ga={with_ga} Q={q} R={r}")
+    rng = np.random.default_rng(d_len * 11 + q)
+    lim = 1 << (q + r - 1)
+    z = rng.integers(-lim, lim, d_len, dtype=np.int64)
+    ga = rng.integers(-lim, lim, d_len, dtype=np.int64) if with_ga else None
+    li = d_len.bit_length() - 1
+    pts = [[int.from_bytes(rng.bytes(40), "little") % R_MOD for _ in range(li)] for _ in range(4)]
+    if li:
+        pts[1][0] = 0            # a corner of the cube and the largest element among the coordinates
+        pts[2][li - 1] = R_MOD - 1
+    tr = lib.Transcript(22)
+    got = lib.zkrelu_prove(ctx, z, ga, tr, q, r, points=pts)
+    ots = OracleTranscript(22)
+    buf, info = P.zkrelu_prove(z.tolist(), ga.tolist() if with_ga else None, q, r, ots, points=pts)
+    assert got["points"] == [x for pt in pts for x in pt] + ots.challenges
+    assert got["proof"] == buf
+    assert got["claims"] == info["c_in"]
+    assert tr.digest() == ots.digest()
+    tv = OracleTranscript(22)
+    P.zkrelu_verify(got["proof"], tv, points=pts)
+    assert tv.digest() == ots.digest()
+
+
+def test_zkrelu_at_rejects_bad_points(lib, ctx):
+    say("zkrelu_at bad points")
+    z = np.arange(4, dtype=np.int64)
+    tr = lib.Transcript(3)
+    before = tr.digest()
+    with pytest.raises(lib.ZkdlError):
+        lib.zkrelu_prove(ctx, z, None, tr, 32, 16, points=[[R_MOD, 0], [0, 0], [0, 0], [0, 0]])
+    assert tr.digest() == before
+
+
 @pytest.mark.parametrize("fill,d_len,with_ga", [(1, 1024, True), (64, 1024, True), (128, 512, False), (4096, 2048, True)])
 def test_zkrelu_column_chunking(lib, fill, d_len, with_ga):
     """The proof does not depend on how the bit columns are cut into chunks.  With a low fill

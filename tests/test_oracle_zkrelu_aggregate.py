@@ -109,6 +109,67 @@ def test_zkrelu_rounds_against_direct_double_sum(d_len, with_ga):
     assert out["aux_claim"]["value"] == mle_eval(aux, out["aux_claim"]["point"])
 
 
+def _direct_double_sum(info, q, r_bits, d_len):
+    """The combined sum of App. A written out over all (i, j), from the witness bits."""
+    wit = info["wit"]
+    s, sp, j_pad = wit["s"], wit["sp"], wit["j_pad"]
+    r, rp = info["r"], info["rp"]
+    total = 0
+    for i in range(d_len):
+        ns = 1 - int(wit["aux0"][i, q + r_bits - 1])
+        bz, ba = beta_eval(info["u_z"], i), beta_eval(info["u_a"], i)
+        bga, bgz = beta_eval(info["u_ga"], i), beta_eval(info["u_gz"], i)
+        for j in range(j_pad):
+            a0, a1 = int(wit["aux0"][i, j]), int(wit["aux1"][i, j])
+            bbin = beta_eval(info["u_bin"], i * j_pad + j)
+            total += (r * r * bz * a0 * s[j] + r * ba * ns * a0 * sp[j] + bbin * (a0 * a0 - a0)
+                      + rp * (r * r * bga * a1 * s[j] + r * bgz * ns * a1 * sp[j] + bbin * (a1 * a1 - a1)))
+    return total % R_MOD
+
+
+@pytest.mark.parametrize("bind", [True, False])
+def test_zkrelu_at_given_points(bind):
+    # the four points of the input claims come from outside (Sec. 3.2: the sumchecks of the
+    # operations that Z, A, G_A, G_Z take part in leave them)
+    q, r_bits, d_len = 5, 3, 8
+    lim = 1 << (q + r_bits - 1)
+    z = rng.integers(-lim, lim, d_len).tolist()
+    ga = rng.integers(-lim, lim, d_len).tolist()
+    pts = [[int.from_bytes(rng.bytes(40), "little") % R_MOD for _ in range(3)] for _ in range(4)]
+    ts = Transcript(21)
+    buf, info = P.zkrelu_prove(z, ga, q, r_bits, ts, points=pts, bind_points=bind)
+    assert [info["u_z"], info["u_a"], info["u_ga"], info["u_gz"]] == pts
+    c = info["c_in"]
+    assert c[0] == mle_eval(fr_array(z), pts[0])
+    assert c[1] == mle_eval(fr_array([((x + 4) >> 3) if x >= 0 else 0 for x in z]), pts[1])
+    assert c[2] == mle_eval(fr_array(ga), pts[2])
+    assert c[3] == mle_eval(fr_array([((g + 4) >> 3) if x >= 0 else 0 for x, g in zip(z, ga)]), pts[3])
+    assert info["proof"].claim0 == _direct_double_sum(info, q, r_bits, d_len)
+    assert buf[20] == (1 if bind else 2)
+    tv = Transcript(21)
+    end, out = P.zkrelu_verify(buf, tv, points=pts)
+    assert end == len(buf) and tv.digest() == ts.digest()
+    # the drawn-points proof is a different transcript; modes cannot be swapped
+    plain, _ = P.zkrelu_prove(z, ga, q, r_bits, Transcript(21))
+    assert plain[20] == 0 and plain[32:] != buf[32:]
+    with pytest.raises(AssertionError):
+        P.zkrelu_verify(buf, Transcript(21))
+    with pytest.raises(AssertionError):
+        P.zkrelu_verify(plain, Transcript(21), points=pts)
+    # any changed coordinate of any point is rejected (bound: other challenges; unbound: the
+    # final check uses the verifier's own points)
+    for k in range(4):
+        bad = [list(pt) for pt in pts]
+        bad[k][1] = (bad[k][1] + 1) % R_MOD
+        with pytest.raises(AssertionError):
+            P.zkrelu_verify(buf, Transcript(21), points=bad)
+    # a proof made in one mode does not verify as the other
+    flipped = bytearray(buf)
+    flipped[20] = 2 if bind else 1
+    with pytest.raises(AssertionError):
+        P.zkrelu_verify(bytes(flipped), Transcript(21), points=pts)
+
+
 def test_zkrelu_forward_only_equals_zero_gradient():
     z = rng.integers(-2 ** 40, 2 ** 40, 4).tolist()
     b1, _ = P.zkrelu_prove(z, None, Q, R, Transcript(2))
