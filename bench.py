@@ -6,7 +6,8 @@ the partial evaluation of a 4096 x 4096 uniform Fr matrix at a random row point.
 Inputs are resident in HBM before the timed region.  Prints one JSON line:
 `value` = Fr elements through the step per second; `config` names the workload and carries the
 median times of its two parts, of the one-layer proofs and of the aggregated proofs of the
-8 x 1024^2 (batch 64; one step and 16 steps) and 4 x 4096^2 (batch 256) networks; `roofline` =
+8 x 1024^2 (batch 64; one step, also with the claims chained, and 16 steps) and 4 x 4096^2
+(batch 256) networks; `roofline` =
 algorithmic bytes of the fused round kernels over their launch time measured with HIP events on
 the library's stream (plus the multiply-add rate and the other kernel classes); `cpu_baseline` =
 the CPU oracle's rate on the host cores.
@@ -203,6 +204,8 @@ def main():
         ag_med, ag_min = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + 3)), 5)
         out["config"]["proof_ms_batch64_8layer_step"] = 1e3 * ag_med
         out["config"]["proof_ms_batch64_8layer_step_min"] = 1e3 * ag_min
+        lk_med, _ = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + 3), linked=True), 5)
+        out["config"]["proof_ms_batch64_8layer_step_linked"] = 1e3 * lk_med
         out["config"]["paper_context"] = ("paper: < 1 s per batch-64 update, 8-layer 10M-parameter net, one "
                                           "Tesla A100, whole protocol including commitments (not comparable)")
         del dw

@@ -259,6 +259,28 @@ typedef struct {
 int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
                     size_t* proof_len, zkdl_fr* points_out, size_t* npoints);
 
+/* aggregate_prove_linked: the same four families with their claims chained (Sec. 3.2: the
+ * claims zkReLU starts from are left by the other operations' sumchecks; Sec. 4, Eq.
+ * sc-reindex: claims on stacks whose slots are shifted become claims on the stack itself;
+ * Protocol zkdl, the sumcheck and re-indexing lines).  In order, on one transcript:
+ *  1. forward, gradA, gradW as in aggregate_prove;
+ *  2. zkReLU at u_Z = the point of forward's claim_0, u_A = the point of forward's final on
+ *     A, u_GA = the point of gradA's claim_0, u_GZ = the point of gradW's final on G_Z
+ *     (header "zkrelu_at" with mode 2: the points are not hashed again);
+ *  3. re-indexing on A [N, B width] with two sub-stacks at forward's stack point v_n: A itself
+ *     and the stack whose slot (t, l) is slot (t, l+1), zero for the last layer (the ReLU
+ *     outputs), common point (u0, v_i);
+ *  4. re-indexing on G_Z and on W with that shifted sub-stack alone, at gradA's stack point,
+ *     common points (u0, v_i) and (u1, v_i).
+ * The re-indexing headers carry N, D, K only.  What the verifier checks between the parts
+ * (c_GA = gradA's claim_0; forward's claim_0 - c_Z and gradW's final on G_Z - c_GZ are the
+ * last layer's share; the sub-stack claims equal the finals and c_A) needs nothing from the
+ * prover.  Proof: "ZKAL" header (L, B, width, T, Q, R, 0), three SC blocks, the zkReLU
+ * proof, three "ZKRI" proofs.  points_out: every challenge in order; the 4 log2(N B width)
+ * coordinates given to zkReLU are repeated in front of its own draws. */
+int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
+                           size_t* proof_len, zkdl_fr* points_out, size_t* npoints);
+
 /* ---- per-kernel timing (for callers that measure; paper-independent) -------
  * While enabled, the launches of the kernel classes below are bracketed by HIP
  * events on the context's stream; zkdl_ctx_profile_read returns, per class and

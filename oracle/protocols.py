@@ -214,6 +214,13 @@ def _reindex_statement_digest(n, d, maps, points, u):
     return h.digest()
 
 
+def _reindex_header(ts, n, d, maps, points, u, bind_statement):
+    if bind_statement:
+        ts.absorb(b"reindex", _reindex_statement_digest(n, d, maps, points, u))
+    else:
+        ts.absorb_u32(b"reindex", [n, d, len(maps)])
+
+
 def reindex_weights(n, maps, points, r):
     """P[i] = sum_k r_k sum_j beta~(u_k, j) p_k(i, j), p_k(i, j) = [maps[k][j] == i]."""
     p = [0] * n
@@ -225,7 +232,7 @@ def reindex_weights(n, maps, points, r):
     return p
 
 
-def reindex_prove(x, n, d, maps, points, u, ts):
+def reindex_prove(x, n, d, maps, points, u, ts, bind_statement=True):
     """K sub-stacks X_k = (X^(maps[k][0]), X^(maps[k][1]), ..) of the stack X [N, D] (an entry
     -1 is a zero tensor: padding), each with a claim X_k~(u_k, u) at its own stack point u_k
     and the common point u over the other dimensions.  With verifier coefficients r_k,
@@ -237,12 +244,15 @@ def reindex_prove(x, n, d, maps, points, u, ts):
     preceding sumchecks); "c" the K claims; one draw of K coefficients; then the product
     sumcheck on (P, X~(., u)) as in product_prove's rounds (its claim_0 = sum_k r_k c_k is
     absorbed like any claim_0).  Proof: "ZKRI", N, D, K, 0, the K claims, one SC block.
+    bind_statement=False is the use inside a larger proof whose transcript already fixes the
+    maps (public architecture) and the points (earlier challenges): "reindex" then carries
+    the three words N, D, K only.
     """
     k_sub = len(maps)
     assert 1 <= k_sub <= 8 and len(points) == k_sub and len(u) == ilog2(d)
     for m, pt in zip(maps, points):
         assert len(pt) == ilog2(len(m)) and all(-1 <= int(j) < n for j in m)
-    ts.absorb(b"reindex", _reindex_statement_digest(n, d, maps, points, u))
+    _reindex_header(ts, n, d, maps, points, u, bind_statement)
     t, _ = partial_eval(x, [n, d], 1, 2, u)                  # X~(i, u) for every i
     t = [int(v) for v in t]
     claims = []
@@ -258,11 +268,11 @@ def reindex_prove(x, n, d, maps, points, u, ts):
     return b"".join(out), dict(claims=claims, r=r, v=vs, inner=proof, weights=p)
 
 
-def reindex_verify(buf, n, d, maps, points, u, ts):
+def reindex_verify(buf, n, d, maps, points, u, ts, bind_statement=True):
     """Returns (the K claims, the point v, the remaining claim X~(v, u))."""
     magic, n_, d_, k_sub = struct.unpack_from("<IIII", buf, 0)
     assert magic == RI_MAGIC and n_ == n and d_ == d and k_sub == len(maps)
-    ts.absorb(b"reindex", _reindex_statement_digest(n, d, maps, points, u))
+    _reindex_header(ts, n, d, maps, points, u, bind_statement)
     claims = [from_le(buf[16 + 32 * k:48 + 32 * k]) for k in range(k_sub)]
     ts.absorb_fr(b"c", claims)
     r = ts.challenges_vec(k_sub)
@@ -587,3 +597,156 @@ def aggregate_verify(buf, ts):
     off, out["zkrelu"] = zkrelu_verify(buf, ts, off)
     assert off == len(buf)
     return out
+
+
+# --------------------------------------------------------------------------
+# the same window with the claims linked (Sec. 3.2, Sec. 4 Eq. sc-reindex, Protocol zkdl)
+# --------------------------------------------------------------------------
+ZKAL_MAGIC = 0x4C414B5A   # "ZKAL"
+
+
+def down_map(n, n_layers):
+    """Sub-stack whose slot (t, l) is slot (t, l+1) of the stack; the last layer's slot is a
+    zero tensor (shift_layers as an index map)."""
+    return [j + 1 if j % n_layers != n_layers - 1 else -1 for j in range(n)]
+
+
+def _linked_zkrelu_points(f, g, h, ln):
+    """u_Z: point of the forward family's claim_0 (on the stacked Z); u_A: point of its final
+    on A; u_GA: point of gradA's claim_0 (it is G_A); u_GZ: point of gradW's final on G_Z."""
+    return [f["w"] + f["u0"] + f["u1"], f["v"][:ln] + f["u0"] + f["v"][ln:],
+            g["w"] + g["u0"] + g["u1"], h["v"][:ln] + h["v"][ln:] + h["u1"]]
+
+
+def _last_layer_factor(stack_point, n_layers):
+    """beta~ of the layer coordinates (the low bits of the slot index) at the last layer."""
+    ll = ilog2(n_layers)
+    lay = stack_point[len(stack_point) - ll:]
+    return beta_point(lay, index_bits(n_layers - 1, ll)) if ll else 1
+
+
+def aggregate_linked_prove(wit, ts):
+    """aggregate_prove's four families with the claims chained instead of left side by side:
+
+    1. forward, gradA, gradW matmul sumchecks as in aggregate_prove.
+    2. zkReLU at the points these have left (_linked_zkrelu_points), unbound mode.  Its input
+       claims c_Z, c_A, c_GA, c_GZ then satisfy, for the verifier to check,
+         c_GA = claim_0 of gradA,
+         claim_0 of forward = c_Z + beta~(w_layer, L-1) Zlast~(w_step, u0, u1),
+         gradW's final on G_Z = c_GZ + beta~(v_layer, L-1) GZlast~(v_step, v_i, u1),
+       (the stacks given to zkReLU are zero in the last layer's slots, which have no ReLU;
+       Zlast / GZlast [T', B, width] are the last layer's outputs and their gradients: the two
+       claims on them are outputs of this proof, computed by the verifier).
+    3. Re-indexing (Eq. sc-reindex) on the stack A with two sub-stacks at the stack point v_n
+       of the forward family: A itself (claim: forward's final on A) and the shifted stack
+       whose slot (t, l) is the input of layer l+1 = the output of this layer's ReLU (claim:
+       c_A).  One claim on A is left.
+    4. Re-indexing on G_Z and on W, one shifted sub-stack each: gradA's finals (they are
+       evaluations of the stacks of the next layer's G_Z and W) become claims on the stacks.
+    Proof: "ZKAL" header, the three SC blocks, the zkReLU proof, the three ZKRI proofs."""
+    n_layers, bsz, width, steps = wit["L"], wit["B"], wit["width"], wit["T"]
+    q, r_bits = wit["Q"], wit["R"]
+    n = n_layers * steps
+    ln = ilog2(n)
+    a = np.asarray(wit["A"]).reshape(n, bsz, width)
+    w = np.asarray(wit["W"]).reshape(n, width, width)
+    gz = np.asarray(wit["GZ"]).reshape(n, bsz, width)
+    ts.absorb_u32(b"aggregate_linked", [n_layers, bsz, width, steps, q, r_bits])
+    parts = [struct.pack("<IIIIIIII", ZKAL_MAGIC, n_layers, bsz, width, steps, q, r_bits, 0)]
+    infos = {}
+    proofs = {}
+    buf, proofs["fwd"], infos["fwd"] = matmul_prove(fr_array(a), [n, bsz, width], fr_array(w),
+                                                    [n, width, width], ts)
+    parts.append(buf)
+    gz_next = shift_layers(gz, n_layers)
+    wt_next = np.transpose(shift_layers(w, n_layers), (0, 2, 1))
+    buf, proofs["gradA"], infos["gradA"] = matmul_prove(fr_array(gz_next), [n, bsz, width],
+                                                        fr_array(wt_next), [n, width, width], ts)
+    parts.append(buf)
+    buf, proofs["gradW"], infos["gradW"] = matmul_prove(fr_array(np.transpose(a, (0, 2, 1))),
+                                                        [n, width, bsz], fr_array(gz), [n, bsz, width], ts)
+    parts.append(buf)
+    f, g, h = infos["fwd"], infos["gradA"], infos["gradW"]
+    pts = _linked_zkrelu_points(f, g, h, ln)
+    buf, infos["zkrelu"] = zkrelu_prove(np.asarray(wit["Zr"]).reshape(-1).tolist(),
+                                        np.asarray(wit["GA"]).reshape(-1).tolist(), q, r_bits, ts,
+                                        points=pts, bind_points=False)
+    parts.append(buf)
+    c_in = infos["zkrelu"]["c_in"]
+    assert c_in[2] == proofs["gradA"].claim0, "G_A of the witness is not the gradA family's product"
+    down = down_map(n, n_layers)
+    vn_f, vi_f = f["v"][:ln], f["v"][ln:]
+    vn_a, vi_a = g["v"][:ln], g["v"][ln:]
+    buf, infos["reindex_A"] = reindex_prove(fr_array(a.reshape(n, -1)), n, bsz * width,
+                                            [list(range(n)), down], [vn_f, vn_f], f["u0"] + vi_f, ts,
+                                            bind_statement=False)
+    assert infos["reindex_A"]["claims"] == [proofs["fwd"].finals[1], c_in[1]], \
+        "the next layer's input is not this layer's ReLU output"
+    parts.append(buf)
+    buf, infos["reindex_GZ"] = reindex_prove(fr_array(gz.reshape(n, -1)), n, bsz * width, [down], [vn_a],
+                                             g["u0"] + vi_a, ts, bind_statement=False)
+    assert infos["reindex_GZ"]["claims"] == [proofs["gradA"].finals[1]]
+    parts.append(buf)
+    buf, infos["reindex_W"] = reindex_prove(fr_array(w.reshape(n, -1)), n, width * width, [down], [vn_a],
+                                            g["u1"] + vi_a, ts, bind_statement=False)
+    assert infos["reindex_W"]["claims"] == [proofs["gradA"].finals[2]]
+    parts.append(buf)
+    return b"".join(parts), infos
+
+
+def aggregate_linked_verify(buf, ts):
+    """Replays the linked proof and checks every link.  Returns the claims that are left, each
+    as (point, value): on A (two), W (two), G_Z (one from the re-indexing; gradW's final is
+    consumed by zkReLU), the last layer's Z and G_Z, G_W, aux."""
+    magic, n_layers, bsz, width, steps, q, r_bits, _ = struct.unpack_from("<IIIIIIII", buf, 0)
+    assert magic == ZKAL_MAGIC
+    n = n_layers * steps
+    ln, lt = ilog2(n), ilog2(steps)
+    ts.absorb_u32(b"aggregate_linked", [n_layers, bsz, width, steps, q, r_bits])
+    off = 32
+    pr, inf = {}, {}
+    for name, (d1, d2, d3) in (("fwd", (bsz, width, width)), ("gradA", (bsz, width, width)),
+                               ("gradW", (width, bsz, width))):
+        _, end = SumcheckProof.from_bytes(buf, off)
+        pr[name], inf[name] = matmul_verify(buf[off:end], n, d1, d2, d3, ts)
+        off = end
+    f, g, h = inf["fwd"], inf["gradA"], inf["gradW"]
+    pts = _linked_zkrelu_points(f, g, h, ln)
+    assert struct.unpack_from("<I", buf, off + 20)[0] == 2, "zkReLU must take its points from this transcript"
+    off, zk = zkrelu_verify(buf, ts, off, points=pts)
+    c_z, c_a, c_ga, c_gz = zk["c_in"]
+    assert c_ga == pr["gradA"].claim0, "G_A link"
+    vn_f, vi_f = f["v"][:ln], f["v"][ln:]
+    vn_a, vi_a = g["v"][:ln], g["v"][ln:]
+    vn_w, vi_w = h["v"][:ln], h["v"][ln:]
+
+    def last_layer_claim(total, part, stack_point):
+        fac = _last_layer_factor(stack_point, n_layers)
+        if fac == 0:                      # the point lies where the last layer has weight 0
+            assert total == part
+            return None
+        return (total - part) * pow(fac, R_MOD - 2, R_MOD) % R_MOD
+    z_last = last_layer_claim(pr["fwd"].claim0, c_z, f["w"])
+    gz_last = last_layer_claim(pr["gradW"].finals[2], c_gz, vn_w)
+    down = down_map(n, n_layers)
+
+    def reindex_at(off, d, maps, points, u):
+        k_sub = len(maps)
+        _, end = SumcheckProof.from_bytes(buf, off + 16 + 32 * k_sub)
+        claims, vs, left = reindex_verify(buf[off:end], n, d, maps, points, u, ts, bind_statement=False)
+        return end, claims, vs, left
+    off, cl, v_ra, a_left = reindex_at(off, bsz * width, [list(range(n)), down], [vn_f, vn_f], f["u0"] + vi_f)
+    assert cl == [pr["fwd"].finals[1], c_a], "A link"
+    off, cl, v_rg, gz_left = reindex_at(off, bsz * width, [down], [vn_a], g["u0"] + vi_a)
+    assert cl == [pr["gradA"].finals[1]], "G_Z link"
+    off, cl, v_rw, w_left = reindex_at(off, width * width, [down], [vn_a], g["u1"] + vi_a)
+    assert cl == [pr["gradA"].finals[2]], "W link"
+    assert off == len(buf)
+    return dict(
+        A=[(v_ra + f["u0"] + vi_f, a_left), (vn_w + vi_w + h["u0"], pr["gradW"].finals[1])],
+        W=[(vn_f + vi_f + f["u1"], pr["fwd"].finals[2]), (v_rw + g["u1"] + vi_a, w_left)],
+        GZ=[(v_rg + g["u0"] + vi_a, gz_left)],
+        Zlast=(f["w"][:lt] + f["u0"] + f["u1"], z_last),
+        GZlast=(vn_w[:lt] + vi_w + h["u1"], gz_last),
+        GW=(h["w"] + h["u0"] + h["u1"], pr["gradW"].claim0),
+        aux=(zk["aux_claim"]["point"], zk["aux_claim"]["value"]))

@@ -893,6 +893,29 @@ static int upload_bytes(zkdl_ctx* ctx, const void* host, size_t n, void** dev_ou
     return ZKDL_OK;
 }
 
+// inverse maps by stack index: counting sort of the (k, j) entries (k in the top 3 bits of an
+// entry, j in the other 29); maps_flat = the maps one after the other
+static void build_inverse_maps(int K, const int32_t* const* maps, const uint64_t* map_len, uint64_t N,
+                               std::vector<uint32_t>& row_off, std::vector<uint32_t>& ent,
+                               std::vector<uint32_t>& maps_flat) {
+    uint64_t total = 0;
+    for (int k = 0; k < K; ++k) total += map_len[k];
+    row_off.assign(N + 1, 0);
+    ent.assign(total ? total : 1, 0);
+    maps_flat.assign(total ? total : 1, 0);
+    for (int k = 0; k < K; ++k)
+        for (uint64_t j = 0; j < map_len[k]; ++j)
+            if (maps[k][j] >= 0) ++row_off[(size_t)maps[k][j] + 1];
+    for (uint64_t i = 0; i < N; ++i) row_off[i + 1] += row_off[i];
+    std::vector<uint32_t> cur(row_off.begin(), row_off.end() - 1);
+    uint64_t f = 0;
+    for (int k = 0; k < K; ++k)
+        for (uint64_t j = 0; j < map_len[k]; ++j) {
+            maps_flat[f++] = (uint32_t)maps[k][j];
+            if (maps[k][j] >= 0) ent[cur[(size_t)maps[k][j]]++] = ((uint32_t)k << 29) | (uint32_t)j;
+        }
+}
+
 extern "C" int reindex_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const int32_t* const* maps,
                              const uint64_t* map_len, const zkdl_fr* const* points, const zkdl_fr* u,
                              zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
@@ -940,21 +963,8 @@ extern "C" int reindex_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const i
         dgw[i] = (uint32_t)dg[4 * i] | ((uint32_t)dg[4 * i + 1] << 8) | ((uint32_t)dg[4 * i + 2] << 16) |
                  ((uint32_t)dg[4 * i + 3] << 24);
 
-    // inverse maps by stack index: counting sort of the (k, j) entries
-    std::vector<uint32_t> row_off(N + 1, 0), ent(total ? total : 1), maps_flat(total ? total : 1);
-    for (int k = 0; k < K; ++k)
-        for (uint64_t j = 0; j < map_len[k]; ++j)
-            if (maps[k][j] >= 0) ++row_off[(size_t)maps[k][j] + 1];
-    for (uint64_t i = 0; i < N; ++i) row_off[i + 1] += row_off[i];
-    {
-        std::vector<uint32_t> cur(row_off.begin(), row_off.end() - 1);
-        uint64_t f = 0;
-        for (int k = 0; k < K; ++k)
-            for (uint64_t j = 0; j < map_len[k]; ++j) {
-                maps_flat[f++] = (uint32_t)maps[k][j];
-                if (maps[k][j] >= 0) ent[cur[(size_t)maps[k][j]]++] = ((uint32_t)k << 29) | (uint32_t)j;
-            }
-    }
+    std::vector<uint32_t> row_off, ent, maps_flat;
+    build_inverse_maps(K, maps, map_len, N, row_off, ent, maps_flat);
 
     int rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
@@ -1153,5 +1163,196 @@ extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_t
     if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tA, &tG, 1, 0, 0, 16, nullptr);
     if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, w->Zr, w->GA, N * w->B * w->width, (int)w->Q, (int)w->R, 0, nullptr);
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
+// ---------------------------------------------------------------------------
+// the same window with the claims linked (Sec. 3.2; Sec. 4, Eq. sc-reindex; Protocol zkdl)
+// ---------------------------------------------------------------------------
+static const uint32_t ZKAL_MAGIC = 0x4C414B5Au;
+
+// The index maps of a re-indexing inside a larger proof (K sub-stacks of N entries each), inverted
+// and copied to the device.  Uploaded before the proof's kernels are enqueued: the copies read
+// pageable memory and would otherwise wait for everything enqueued before them.
+struct RiPrepared {
+    int K = 0;
+    void *d_row = nullptr, *d_ent = nullptr, *d_maps = nullptr;
+    std::vector<uint32_t> row_off, ent, maps_flat;   // live until the stream has drained
+};
+
+static int prepare_reindex_linked(zkdl_ctx* ctx, uint64_t N, int K, const std::vector<int32_t>* maps,
+                                  RiPrepared& out) {
+    const int32_t* mp[ZKDL_REINDEX_MAX_K];
+    uint64_t lens[ZKDL_REINDEX_MAX_K];
+    for (int k = 0; k < K; ++k) {
+        mp[k] = maps[k].data();
+        lens[k] = N;
+    }
+    out.K = K;
+    build_inverse_maps(K, mp, lens, N, out.row_off, out.ent, out.maps_flat);
+    const uint64_t total = (uint64_t)K * N;
+    int rc = upload_bytes(ctx, out.row_off.data(), (N + 1) * 4, &out.d_row);
+    if (rc == ZKDL_OK) rc = upload_bytes(ctx, out.ent.data(), total * 4, &out.d_ent);
+    if (rc == ZKDL_OK) rc = upload_bytes(ctx, out.maps_flat.data(), total * 4, &out.d_maps);
+    return rc;
+}
+
+static void free_reindex_linked(zkdl_ctx* ctx, RiPrepared& p) {
+    zk_free(ctx, p.d_row);
+    zk_free(ctx, p.d_ent);
+    zk_free(ctx, p.d_maps);
+}
+
+// One re-indexing sumcheck inside a larger proof: the stack X [N, D] of int32, the sub-stacks of
+// `maps`, every stack point = the ln challenges from chal[point_chal[k]] on, the common point u =
+// the ld challenges listed in u_idx.  The header frame carries N, D, K only (maps and points are
+// fixed by the transcript so far).  The work memory is handed back in `keep` and must live until
+// the stream has drained.
+static int enqueue_reindex_linked(zkdl_ctx* ctx, const int32_t* X, uint64_t N, uint64_t rows, uint64_t cols,
+                                  const RiPrepared& maps, const int* point_chal, const ChalIdx& u_idx,
+                                  std::vector<void*>& keep) {
+    const uint64_t D = rows * cols;
+    const int ln = ilog2_u64(N), lr = ilog2_u64(rows), ld = ilog2_u64(D), K = maps.K;
+    if (ld > ZK_CHAL_SET_MAX || ctx->n_chal + K + ln > ZK_MAX_CHAL - ZK_CHAL_SET_MAX) return ZKDL_EINVAL;
+    const uint64_t total = (uint64_t)K * N;
+    uint32_t hw[3] = {(uint32_t)N, (uint32_t)D, (uint32_t)K};
+    zk_absorb_words(ctx, "reindex", hw, 3);
+    uint32_t hdr[4] = {ZKRI_MAGIC, (uint32_t)N, (uint32_t)D, (uint32_t)K};
+    zk_write_proof_words(ctx, hdr, 4);
+    // the coordinates of u, gathered behind the challenges this call can draw
+    const int u_at = ZK_MAX_CHAL - ZK_CHAL_SET_MAX;
+    zk_launch_chal_set(ctx, u_at, ld, nullptr, &u_idx);
+    const Fr* chal = ctx->dev->chal;
+    // X~(n, u) in two steps, columns then rows: N * rows dot products of length cols keep the
+    // machine busy where N products of length rows * cols would not
+    void* mem = zk_alloc(ctx, (rows + cols + N * rows + total + 2 * N) * 32 + zk_sumcheck_work_bytes(2, ln));
+    if (!mem) return ZKDL_ENOMEM;
+    keep.push_back(mem);
+    uint32_t* w = (uint32_t*)mem;
+    BetaJob jobs[ZKDL_REINDEX_MAX_K + 2];
+    ReindexJob job;
+    job.K = K;
+    jobs[0].point = chal + u_at;
+    jobs[0].m = lr;
+    jobs[0].out = make_tab(w, rows);
+    w += 8 * rows;
+    jobs[1].point = chal + u_at + lr;
+    jobs[1].m = ld - lr;
+    jobs[1].out = make_tab(w, cols);
+    w += 8 * cols;
+    const FrTab by_row = make_tab(w, N * rows);
+    w += 8 * N * rows;
+    for (int k = 0; k < K; ++k) {
+        jobs[2 + k].point = chal + point_chal[k];
+        jobs[2 + k].m = ln;
+        jobs[2 + k].out = make_tab(w, N);
+        job.map[k] = (const int32_t*)maps.d_maps + (uint64_t)k * N;
+        job.len[k] = N;
+        job.beta[k] = jobs[2 + k].out;
+        w += 8 * N;
+    }
+    job.row_off = (const uint32_t*)maps.d_row;
+    job.ent = (const uint32_t*)maps.d_ent;
+    const FrTab T = make_tab(w, N);
+    w += 8 * N;
+    const FrTab P = make_tab(w, N);
+    w += 8 * N;
+    int rc = zk_build_beta_many(ctx, jobs, K + 2);
+    if (rc == ZKDL_OK) rc = zk_partial_eval(ctx, TK_I32, X, N * rows, cols, 1, jobs[1].out, by_row);
+    if (rc == ZKDL_OK) rc = zk_partial_eval(ctx, TK_FR, &by_row, N, rows, 1, jobs[0].out, T);
+    if (rc == ZKDL_OK) rc = zk_reindex(ctx, job, T, P, ln, w);
+    return rc;
+}
+
+extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr,
+                                      uint8_t* proof, size_t* proof_len, zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !w || !tr || !w->A || !w->W || !w->GZ || !w->Zr || !w->GA) return ZKDL_EINVAL;
+    if (!is_pow2(w->L) || !is_pow2(w->B) || !is_pow2(w->width) || !is_pow2(w->T)) return ZKDL_EINVAL;
+    const uint64_t N = (uint64_t)w->L * w->T;
+    const int ln = ilog2_u64(N), lb = ilog2_u64(w->B), lw = ilog2_u64(w->width);
+    const int li = ln + lb + lw;
+    if (4 * li > ZK_CHAL_SET_MAX || N > ((uint64_t)1 << 28)) return ZKDL_EINVAL;
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    // the index maps of the three re-indexings: the stack itself, and the stack whose slot (t, l)
+    // is slot (t, l+1), zero for the last layer
+    RiPrepared maps_a, maps_down;
+    {
+        std::vector<int32_t> both[2] = {std::vector<int32_t>(N), std::vector<int32_t>(N)};
+        for (uint64_t j = 0; j < N; ++j) {
+            both[0][j] = (int32_t)j;
+            both[1][j] = (j % w->L != w->L - 1) ? (int32_t)(j + 1) : -1;
+        }
+        rc = prepare_reindex_linked(ctx, N, 2, both, maps_a);
+        if (rc == ZKDL_OK) rc = prepare_reindex_linked(ctx, N, 1, both + 1, maps_down);
+    }
+    uint32_t hw[6] = {w->L, w->B, w->width, w->T, w->Q, w->R};
+    zk_absorb_words(ctx, "aggregate_linked", hw, 6);
+    uint32_t hdr[8] = {ZKAL_MAGIC, w->L, w->B, w->width, w->T, w->Q, w->R, 0};
+    zk_write_proof_words(ctx, hdr, 8);
+    uint64_t sa[3] = {N, w->B, w->width}, sw[3] = {N, w->width, w->width};
+    zkdl_tensor tA = {TK_I32, 3, {sa[0], sa[1], sa[2], 1}, N * w->B * w->width, (void*)w->A, false};
+    zkdl_tensor tG = {TK_I32, 3, {sa[0], sa[1], sa[2], 1}, N * w->B * w->width, (void*)w->GZ, false};
+    zkdl_tensor tW = {TK_I32, 3, {sw[0], sw[1], sw[2], 1}, N * w->width * w->width, (void*)w->W, false};
+    // challenges of a family: w (ln), u0 (l1), u1 (l3), then the rounds v_n (ln), v_i (l2)
+    const int cf = ctx->n_chal;                       // forward: l1 = lb, l2 = lw, l3 = lw
+    if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tA, &tW, 0, 0, 0, 8, nullptr);
+    const int ca = ctx->n_chal;                       // gradA: the same shape
+    if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tG, &tW, 0, 1, w->L, 12, nullptr);
+    const int cw = ctx->n_chal;                       // gradW: l1 = lw, l2 = lb, l3 = lw
+    if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tA, &tG, 1, 0, 0, 16, nullptr);
+    const int f_u0 = cf + ln, f_vn = cf + ln + lb + lw, f_vi = f_vn + ln;
+    const int a_u0 = ca + ln, a_u1 = a_u0 + lb, a_vn = ca + ln + lb + lw, a_vi = a_vn + ln;
+    const int w_u1 = cw + ln + lw, w_vn = cw + ln + lw + lw, w_vi = w_vn + ln;
+    std::vector<void*> keep;
+    if (rc == ZKDL_OK) {
+        // zkReLU at the points the three families have left: u_Z = point of forward's claim_0,
+        // u_A = point of its final on A, u_GA = point of gradA's claim_0, u_GZ = point of gradW's
+        // final on G_Z
+        ChalIdx idx = {};
+        int at = 0;
+        auto put = [&](int from, int count) {
+            for (int i = 0; i < count; ++i) idx.v[at++] = (int16_t)(from + i);
+        };
+        put(cf, li);
+        put(f_vn, ln), put(f_u0, lb), put(f_vi, lw);
+        put(ca, li);
+        put(w_vn, ln), put(w_vi, lb), put(w_u1, lw);
+        if (ctx->n_chal + 4 * li > ZK_MAX_CHAL) rc = ZKDL_EINVAL;
+        if (rc == ZKDL_OK) {
+            zk_launch_chal_set(ctx, ctx->n_chal, 4 * li, nullptr, &idx);
+            rc = enqueue_zkrelu(ctx, w->Zr, w->GA, N * w->B * w->width, (int)w->Q, (int)w->R, 2, nullptr);
+        }
+    }
+    if (rc == ZKDL_OK) {
+        // A: itself and its shifted stack (the ReLU outputs) at forward's stack point, u = (u0, v_i)
+        {
+            const int pts[2] = {f_vn, f_vn};
+            ChalIdx u = {};
+            for (int i = 0; i < lb; ++i) u.v[i] = (int16_t)(f_u0 + i);
+            for (int i = 0; i < lw; ++i) u.v[lb + i] = (int16_t)(f_vi + i);
+            rc = enqueue_reindex_linked(ctx, w->A, N, w->B, w->width, maps_a, pts, u, keep);
+        }
+        // G_Z: gradA's first final is an evaluation of the shifted stack, u = (u0, v_i)
+        if (rc == ZKDL_OK) {
+            const int pts[1] = {a_vn};
+            ChalIdx u = {};
+            for (int i = 0; i < lb; ++i) u.v[i] = (int16_t)(a_u0 + i);
+            for (int i = 0; i < lw; ++i) u.v[lb + i] = (int16_t)(a_vi + i);
+            rc = enqueue_reindex_linked(ctx, w->GZ, N, w->B, w->width, maps_down, pts, u, keep);
+        }
+        // W: gradA's second final is an evaluation of the shifted, transposed stack: rows take u1
+        if (rc == ZKDL_OK) {
+            const int pts[1] = {a_vn};
+            ChalIdx u = {};
+            for (int i = 0; i < lw; ++i) u.v[i] = (int16_t)(a_u1 + i);
+            for (int i = 0; i < lw; ++i) u.v[lw + i] = (int16_t)(a_vi + i);
+            rc = enqueue_reindex_linked(ctx, w->W, N, w->width, w->width, maps_down, pts, u, keep);
+        }
+    }
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
+    for (void* p : keep) zk_free(ctx, p);
+    free_reindex_linked(ctx, maps_a);
+    free_reindex_linked(ctx, maps_down);
     return rc != ZKDL_OK ? rc : rc2;
 }

@@ -93,6 +93,17 @@ def aggregate_case():
             "digest_hex": ts.digest().hex()}
 
 
+def aggregate_linked_case():
+    """The same window with the claims chained (Sec. 3.2; Eq. sc-reindex; Protocol zkdl)."""
+    wit = fcnn_window(2307162730 + 90, 2, 4, 2, 2)
+    ts = Transcript(13)
+    buf, _ = P.aggregate_linked_prove(wit, ts)
+    return {"protocol": "aggregate_prove_linked", "cite": "Sec. 3.2, Eq. sc-reindex, Protocol zkdl", "seed": 13,
+            "workload": "fcnn_window(2307162730 + 90, n_layers=2, width=4, batch=2, steps=2)",
+            "proof_hex": bytes(buf).hex(), "challenges": [hex(v) for v in ts.challenges],
+            "digest_hex": ts.digest().hex()}
+
+
 def reindex_case():
     """Re-indexing sumcheck (Eq. sc-reindex): stack of N = 4 tensors of D = 8, two sub-stacks."""
     rng = np.random.default_rng(20230718)
@@ -113,6 +124,7 @@ if __name__ == "__main__":
                      ("matmul_ft_n2_2x4x2", matmul_ft_case),
                      ("zkrelu_d4_q5_r3", zkrelu_case), ("zkrelu_at_d4_q5_r3", zkrelu_at_case),
                      ("aggregate_l2_w4_b2_t2", aggregate_case),
+                     ("aggregate_linked_l2_w4_b2_t2", aggregate_linked_case),
                      ("reindex_n4_d8_k2", reindex_case)):
         with open(os.path.join(HERE, name + ".json"), "w") as f:
             json.dump(fn(), f, indent=1)

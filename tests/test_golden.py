@@ -37,13 +37,27 @@ def oracle_run(g):
         pts = [[int(v) for v in fr_array_from_le(bytes.fromhex(h), len(h) // 64)] for h in g["points_le_hex"]]
         u = [int(v) for v in fr_array_from_le(bytes.fromhex(g["u_le_hex"]), len(g["u_le_hex"]) // 64)]
         buf = P.reindex_prove(fr_array(np.array(g["x"]).reshape(n, d)), n, d, g["maps"], pts, u, ts)[0]
+    elif g["protocol"] == "aggregate_prove_linked":
+        buf = P.aggregate_linked_prove(fcnn_window(2307162730 + 90, 2, 4, 2, 2), ts)[0]
     else:
         out = P.aggregate_prove(fcnn_window(2307162730 + 90, 2, 4, 2, 2), ts)
         buf = out[0] if isinstance(out, tuple) else out
     return bytes(buf), ts
 
 
+def _without_repeats(points, drawn):
+    """Removes from `points` the block of repeated earlier challenges (the points handed to
+    zkReLU), so that the drawn ones remain in order."""
+    out, k = [], 0
+    for v in points:
+        if k < len(drawn) and v == drawn[k]:
+            out.append(v)
+            k += 1
+    return out
+
+
 NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "zkrelu_d4_q5_r3", "zkrelu_at_d4_q5_r3", "aggregate_l2_w4_b2_t2",
+         "aggregate_linked_l2_w4_b2_t2",
          "reindex_n4_d8_k2"]
 
 
@@ -89,7 +103,12 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
         dw = {k: wit[k] for k in ("L", "B", "width", "T", "Q", "R")}
         for k in ("A", "W", "GZ", "Zr", "GA"):
             dw[k] = torch.from_numpy(np.ascontiguousarray(wit[k])).cuda()
-        got = lib.aggregate_prove(ctx, dw, tr)
+        got = lib.aggregate_prove(ctx, dw, tr, linked=g["protocol"] == "aggregate_prove_linked")
+    if g["protocol"] == "aggregate_prove_linked":
+        # the four points given to zkReLU are not draws: they come back in front of its own
+        drawn = {int(v, 16) for v in g["challenges"]}
+        assert [v for v in got["points"] if v not in drawn] == []
+        got["points"] = _without_repeats(got["points"], [int(v, 16) for v in g["challenges"]])
     assert got["proof"].hex() == g["proof_hex"]
     assert [hex(v) for v in got["points"]] == given + g["challenges"]
     assert tr.digest().hex() == g["digest_hex"]

@@ -475,6 +475,27 @@ def test_aggregate(lib, ctx, layers, width, batch, steps):
     P.aggregate_verify(got["proof"], OracleTranscript(33))
 
 
+@pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 32, 8, 1), (1, 16, 2, 1), (2, 4, 2, 4),
+                                                      (4, 16, 8, 4)])
+def test_aggregate_linked(lib, ctx, layers, width, batch, steps):
+    """The four families with their claims chained: zkReLU at the points the matmul sumchecks
+    leave, re-indexing for the shifted stacks."""
+    say(f"aggregate linked L={layers} w={width} B={batch} T={steps}")
+    wit = fcnn_window(CONFIG_SEED + 60 + layers, layers, width, batch, steps)
+    tr = lib.Transcript(34)
+    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr, linked=True)
+    ots = OracleTranscript(34)
+    buf, infos = P.aggregate_linked_prove(wit, ots)
+    assert got["proof"] == buf
+    assert tr.digest() == ots.digest()
+    # the library repeats the four given points in front of zkReLU's own draws
+    before = sum(len(infos[k][c]) for k in ("fwd", "gradA", "gradW") for c in ("w", "u0", "u1", "v"))
+    zk = infos["zkrelu"]
+    given = zk["u_z"] + zk["u_a"] + zk["u_ga"] + zk["u_gz"]
+    assert got["points"] == ots.challenges[:before] + given + ots.challenges[before:]
+    P.aggregate_linked_verify(got["proof"], OracleTranscript(34))
+
+
 def test_config1_fc_layer_plus_relu(lib, ctx):
     """One FC layer + ReLU: X 16x256, W 256x256, zkReLU over Z with Q=32 (forward only)."""
     import torch
@@ -643,6 +664,40 @@ def test_config3_aggregate_by_properties(lib, ctx):
             mask = ((arr >> j) & 1).astype(bool)
             total += bk * int(b_j[j]) % R_MOD * int(b_i[mask].sum() % R_MOD)
     assert value == total % R_MOD
+
+
+def _stack_mle(stack, pn, pr, pc):
+    """X~(pn, pr, pc) of an integer stack [N, rows, cols], one slot at a time."""
+    from oracle.mle import beta_table
+    bn, br, bc = beta_table(pn), beta_table(pr), beta_table(pc)
+    total = 0
+    for k in range(stack.shape[0]):
+        rows = np.dot(stack[k].astype(object), bc) % R_MOD
+        total += int(bn[k]) * int(np.dot(br, rows) % R_MOD)
+    return total % R_MOD
+
+
+def test_config3_aggregate_linked_by_properties(lib, ctx):
+    """8 layers x 1024, batch 64 with the claims chained: the oracle's verifier accepts the proof,
+    checks every link and ends in the same transcript state; each claim that is left is the MLE
+    of the stack it names, evaluated here from the witness."""
+    say("config 3 linked aggregate (8 x 1024^2, batch 64)")
+    wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)
+    tr = lib.Transcript(CONFIG_SEED + 4)
+    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr, linked=True)
+    ots = OracleTranscript(CONFIG_SEED + 4)
+    left = P.aggregate_linked_verify(got["proof"], ots)
+    assert tr.digest() == ots.digest()
+    ln, lb = 3, 6
+    for name in ("A", "GZ", "W"):
+        rows_bits = lb if name != "W" else 10
+        for point, value in left[name]:
+            assert value == _stack_mle(wit[name], point[:ln], point[ln:ln + rows_bits], point[ln + rows_bits:]), name
+    z_last = wit["A"][7].astype(np.int64) @ wit["W"][7].astype(np.int64)
+    point, value = left["Zlast"]
+    assert value == _stack_mle(z_last[None], [], point[:lb], point[lb:])
+    point, value = left["GZlast"]
+    assert value == _stack_mle(wit["GZ"][7:8], [], point[:lb], point[lb:])
 
 
 @pytest.mark.parametrize("name,layers,width,batch,steps,cfg", [

@@ -1,4 +1,6 @@
 """Pins for the oracle's zkReLU and aggregated proofs."""
+import struct
+
 import numpy as np
 import pytest
 
@@ -254,3 +256,68 @@ def test_aggregate_small_network():
         if k % 2 == 0:
             assert (a_next[k] == wit["A"][k + 1]).all()
             assert (gz_prev[k] == wit["GZ"][k]).all()
+
+
+@pytest.mark.parametrize("n_layers,width,batch,steps", [(2, 8, 4, 2), (4, 4, 2, 1), (2, 4, 2, 4)])
+def test_aggregate_linked_claims_are_evaluations_of_the_stacks(n_layers, width, batch, steps):
+    """Every claim the linked proof leaves is the MLE of the tensor it names at the point it
+    names (Sec. 4: one sumcheck's outputs are the next one's inputs; Eq. sc-reindex for the
+    shifted stacks)."""
+    wit = fcnn_window(CONFIG_SEED + 200 + n_layers, n_layers=n_layers, width=width, batch=batch, steps=steps)
+    n = n_layers * steps
+    ts = Transcript(13)
+    buf, infos = P.aggregate_linked_prove(wit, ts)
+    tv = Transcript(13)
+    left = P.aggregate_linked_verify(buf, tv)
+    assert tv.digest() == ts.digest()
+    a, wt, gz = (np.asarray(wit[k]).astype(object) for k in ("A", "W", "GZ"))
+    for name, stack in (("A", a), ("W", wt), ("GZ", gz)):
+        for point, value in left[name]:
+            assert value == mle_eval(fr_array(stack), point), name
+    z = np.einsum("nij,njk->nik", a, wt)
+    point, value = left["Zlast"]
+    assert value == mle_eval(fr_array(z[n_layers - 1::n_layers]), point)
+    point, value = left["GZlast"]
+    assert value == mle_eval(fr_array(gz[n_layers - 1::n_layers]), point)
+    point, value = left["GW"]
+    assert value == mle_eval(fr_array(np.einsum("nbi,nbk->nik", a, gz)), point)
+    # zkReLU ran at the points the matmul sumchecks left, on the stacks the witness holds
+    f = infos["fwd"]
+    ln = ilog2(n)
+    zk = infos["zkrelu"]
+    assert zk["u_z"] == f["w"] + f["u0"] + f["u1"] and zk["u_a"] == f["v"][:ln] + f["u0"] + f["v"][ln:]
+    assert zk["c_in"][0] == mle_eval(fr_array(np.asarray(wit["Zr"])), zk["u_z"])
+    # the shifted stack of A is what ReLU put out
+    a_out = np.zeros_like(a)
+    for k in range(n):
+        if k % n_layers != n_layers - 1:
+            a_out[k] = a[k + 1]
+    assert zk["c_in"][1] == mle_eval(fr_array(a_out), zk["u_a"])
+    # any flipped byte is rejected
+    for off in (40, 32 + 16 + 5, len(buf) // 3, len(buf) // 2, 2 * len(buf) // 3, len(buf) - 40, len(buf) - 1):
+        bad = bytearray(buf)
+        bad[off] ^= 1
+        with pytest.raises((AssertionError, struct.error, ValueError)):
+            P.aggregate_linked_verify(bytes(bad), Transcript(13))
+
+
+def test_aggregate_linked_prover_refuses_an_inconsistent_window():
+    base = fcnn_window(CONFIG_SEED + 202, n_layers=2, width=4, batch=2, steps=2)
+    # the input of layer 2 is not the ReLU output of layer 1
+    wit = dict(base)
+    wit["A"] = np.array(base["A"], copy=True)
+    wit["A"][1, 0, 0] += 1
+    with pytest.raises(AssertionError):
+        P.aggregate_linked_prove(wit, Transcript(1))
+    # G_A is not the product of the next layer's G_Z and W
+    wit = dict(base)
+    wit["GA"] = np.array(base["GA"], copy=True)
+    wit["GA"][0, 0, 0] += 1 << 16
+    with pytest.raises(AssertionError):
+        P.aggregate_linked_prove(wit, Transcript(1))
+    # a weight of layer 2 changed after the gradient was taken
+    wit = dict(base)
+    wit["W"] = np.array(base["W"], copy=True)
+    wit["W"][1, 0, 0] += 1
+    with pytest.raises(AssertionError):
+        P.aggregate_linked_prove(wit, Transcript(1))
