@@ -211,6 +211,23 @@ int reindex_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const int32_t* con
                   zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
                   zkdl_fr* points_out, size_t* npoints);
 
+/* claims_merge_prove: K <= 8 claims X~(p_k) on one tensor X (2^d entries, every p_k over all d
+ * variables, most significant index bit first) become one claim X~(v).  With coefficients r_k
+ * from the verifier,  sum_k r_k X~(p_k) = sum_b P[b] X(b),  P = sum_k r_k beta~(p_k, .), by the
+ * definition of the multilinear extension (Sec. 2.2); it is Eq. sc-reindex with every sub-stack
+ * the stack itself and the sum taken over all variables, and yields the single evaluation per
+ * stack that Protocol zkdl opens.  A product sumcheck on (P, X) proves it; the verifier
+ * computes P~(v) = sum_k r_k beta~(p_k, v).
+ * points (host): K arrays of d canonical elements.  claims (host, K + 2, may be NULL): the K
+ * claims, P~(v), X~(v).  Transcript: "merge" with the SHA-256 digest of u32le d, K and the
+ * points' bytes; "c" the K claims; one draw of K coefficients; the product sumcheck (claim_0,
+ * rounds, finals).  Proof: "ZKMG", d, K, 0, the K claims, one SC block.
+ * Errors: ZKDL_EINVAL for a size that is no power of two or above 2^30, K out of range, a
+ * NULL or non-canonical point. */
+int claims_merge_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const zkdl_fr* const* points,
+                       zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
+                       zkdl_fr* points_out, size_t* npoints);
+
 /* zkrelu_prove: the combined sumcheck of App. A over aux in {0,1}^{2 x D x (Q+R)}
  * (bit axis padded to a power of two), weights r^2, r, 1, r'r^2, r'r, r', then the
  * merge of the three claims on aux into one.  Z, GA: D signed (Q+R)-bit
@@ -271,12 +288,15 @@ int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* 
  *     and the stack whose slot (t, l) is slot (t, l+1), zero for the last layer (the ReLU
  *     outputs), common point (u0, v_i);
  *  4. re-indexing on G_Z and on W with that shifted sub-stack alone, at gradA's stack point,
- *     common points (u0, v_i) and (u1, v_i).
- * The re-indexing headers carry N, D, K only.  What the verifier checks between the parts
+ *     common points (u0, v_i) and (u1, v_i);
+ *  5. the two claims standing on A (from 3, and gradW's final on A^T) merged into one as in
+ *     claims_merge_prove, then the two on W (forward's final, and the one from 4).
+ * One claim per stack is left.  The re-indexing headers carry N, D, K only, the merge headers
+ * d, K only.  What the verifier checks between the parts
  * (c_GA = gradA's claim_0; forward's claim_0 - c_Z and gradW's final on G_Z - c_GZ are the
  * last layer's share; the sub-stack claims equal the finals and c_A) needs nothing from the
  * prover.  Proof: "ZKAL" header (L, B, width, T, Q, R, 0), three SC blocks, the zkReLU
- * proof, three "ZKRI" proofs.  points_out: every challenge in order; the 4 log2(N B width)
+ * proof, three "ZKRI" proofs, two "ZKMG" proofs.  points_out: every challenge in order; the 4 log2(N B width)
  * coordinates given to zkReLU are repeated in front of its own draws. */
 int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
                            size_t* proof_len, zkdl_fr* points_out, size_t* npoints);

@@ -287,6 +287,73 @@ def reindex_verify(buf, n, d, maps, points, u, ts, bind_statement=True):
 
 
 # --------------------------------------------------------------------------
+# several claims on one tensor -> one (the identity behind Eq. sc-reindex, taken over all
+# variables: Protocol zkdl ends with ONE evaluation per stack to be opened)
+# --------------------------------------------------------------------------
+MG_MAGIC = 0x474D4B5A   # "ZKMG"
+
+
+def _merge_header(ts, d, points, bind_statement):
+    if bind_statement:
+        import hashlib
+        h = hashlib.sha256(struct.pack("<II", d, len(points)))
+        for pt in points:
+            h.update(b"".join(to_le(x) for x in pt))
+        ts.absorb(b"merge", h.digest())
+    else:
+        ts.absorb_u32(b"merge", [d, len(points)])
+
+
+def merge_weights(points, r):
+    """P[b] = sum_k r_k beta~(p_k, b)."""
+    p = np.zeros(1 << len(points[0]), dtype=object)
+    for rk, pt in zip(r, points):
+        p = (p + rk * beta_table(pt)) % R_MOD
+    return p
+
+
+def merge_prove(x, points, ts, bind_statement=True):
+    """K claims X~(p_k) on one tensor X (2^d entries, every p_k over all d variables) become
+    one: with verifier coefficients r_k,
+      sum_k r_k X~(p_k) = sum_b P[b] X(b),  P = merge_weights(points, r),
+    by the definition of the multilinear extension; a sumcheck over b (two tables, degree 2)
+    leaves the single claim X~(v), and the verifier evaluates P~(v) = sum_k r_k beta~(p_k, v)
+    itself.  It is Eq. sc-reindex with every sub-stack the stack itself and no common point.
+    Transcript: "merge" (digest of d, K and the points; inside a larger proof that fixes the
+    points, the two words d, K); "c" the K claims; one draw of K coefficients; the product
+    sumcheck.  Proof: "ZKMG", d, K, 0, the K claims, one SC block."""
+    d = ilog2(len(x))
+    k_sub = len(points)
+    assert 1 <= k_sub <= 8 and all(len(pt) == d for pt in points)
+    _merge_header(ts, d, points, bind_statement)
+    claims = [mle_eval(x, pt) for pt in points]
+    ts.absorb_fr(b"c", claims)
+    r = ts.challenges_vec(k_sub)
+    proof, vs = prove([merge_weights(points, r), np.asarray(x, dtype=object)], [(1, [0, 1])], 2, ts)
+    assert proof.claim0 == sum(rk * ck for rk, ck in zip(r, claims)) % R_MOD
+    out = [struct.pack("<IIII", MG_MAGIC, d, k_sub, 0)] + [to_le(c) for c in claims] + [proof.to_bytes()]
+    return b"".join(out), dict(claims=claims, r=r, v=vs, inner=proof)
+
+
+def merge_verify(buf, d, points, ts, bind_statement=True):
+    """Returns (the K claims, the point v, the remaining claim X~(v))."""
+    magic, d_, k_sub, _ = struct.unpack_from("<IIII", buf, 0)
+    assert magic == MG_MAGIC and d_ == d and k_sub == len(points)
+    _merge_header(ts, d, points, bind_statement)
+    claims = [from_le(buf[16 + 32 * k:48 + 32 * k]) for k in range(k_sub)]
+    ts.absorb_fr(b"c", claims)
+    r = ts.challenges_vec(k_sub)
+    proof, end = SumcheckProof.from_bytes(buf, 16 + 32 * k_sub)
+    assert end == len(buf) and proof.n_finals == 2 and proof.degree == 2 and len(proof.rounds) == d
+    expect0 = sum(rk * ck for rk, ck in zip(r, claims)) % R_MOD
+    last, vs = verify_rounds(proof, ts, expected_claim0=expect0)
+    pw, xw = proof.finals
+    assert pw * xw % R_MOD == last, "final claim mismatch"
+    assert pw == sum(rk * beta_point(pt, vs) for rk, pt in zip(r, points)) % R_MOD, "P~(v) mismatch"
+    return claims, vs, xw
+
+
+# --------------------------------------------------------------------------
 # batched Hadamard product (Eq. exm-hadamard-batched)
 # --------------------------------------------------------------------------
 def hadamard_prove(x0, x1, ts):
@@ -643,7 +710,11 @@ def aggregate_linked_prove(wit, ts):
        c_A).  One claim on A is left.
     4. Re-indexing on G_Z and on W, one shifted sub-stack each: gradA's finals (they are
        evaluations of the stacks of the next layer's G_Z and W) become claims on the stacks.
-    Proof: "ZKAL" header, the three SC blocks, the zkReLU proof, the three ZKRI proofs."""
+    5. The two claims now standing on A (from 3 and gradW's final on A^T) are merged into one,
+       and so are the two on W (forward's final and the one from 4): merge_prove.
+    One claim per stack is left (Protocol zkdl opens one evaluation per stack).
+    Proof: "ZKAL" header, the three SC blocks, the zkReLU proof, the three ZKRI proofs, the
+    two ZKMG proofs."""
     n_layers, bsz, width, steps = wit["L"], wit["B"], wit["width"], wit["T"]
     q, r_bits = wit["Q"], wit["R"]
     n = n_layers * steps
@@ -691,12 +762,23 @@ def aggregate_linked_prove(wit, ts):
                                             g["u1"] + vi_a, ts, bind_statement=False)
     assert infos["reindex_W"]["claims"] == [proofs["gradA"].finals[2]]
     parts.append(buf)
+    vn_w, vi_w = h["v"][:ln], h["v"][ln:]
+    buf, infos["merge_A"] = merge_prove(fr_array(a.reshape(-1)),
+                                        [infos["reindex_A"]["v"] + f["u0"] + vi_f, vn_w + vi_w + h["u0"]],
+                                        ts, bind_statement=False)
+    assert infos["merge_A"]["claims"] == [infos["reindex_A"]["inner"].finals[1], proofs["gradW"].finals[1]]
+    parts.append(buf)
+    buf, infos["merge_W"] = merge_prove(fr_array(w.reshape(-1)),
+                                        [vn_f + vi_f + f["u1"], infos["reindex_W"]["v"] + g["u1"] + vi_a],
+                                        ts, bind_statement=False)
+    assert infos["merge_W"]["claims"] == [proofs["fwd"].finals[2], infos["reindex_W"]["inner"].finals[1]]
+    parts.append(buf)
     return b"".join(parts), infos
 
 
 def aggregate_linked_verify(buf, ts):
     """Replays the linked proof and checks every link.  Returns the claims that are left, each
-    as (point, value): on A (two), W (two), G_Z (one from the re-indexing; gradW's final is
+    as (point, value): one on A, one on W, one on G_Z (from the re-indexing; gradW's final is
     consumed by zkReLU), the last layer's Z and G_Z, G_W, aux."""
     magic, n_layers, bsz, width, steps, q, r_bits, _ = struct.unpack_from("<IIIIIIII", buf, 0)
     assert magic == ZKAL_MAGIC
@@ -741,10 +823,20 @@ def aggregate_linked_verify(buf, ts):
     assert cl == [pr["gradA"].finals[1]], "G_Z link"
     off, cl, v_rw, w_left = reindex_at(off, width * width, [down], [vn_a], g["u1"] + vi_a)
     assert cl == [pr["gradA"].finals[2]], "W link"
+
+    def merge_at(off, d, points):
+        _, end = SumcheckProof.from_bytes(buf, off + 16 + 32 * len(points))
+        claims, vs, left = merge_verify(buf[off:end], d, points, ts, bind_statement=False)
+        return end, claims, vs, left
+    lb, lw = ilog2(bsz), ilog2(width)
+    off, cl, v_ma, a_one = merge_at(off, ln + lb + lw, [v_ra + f["u0"] + vi_f, vn_w + vi_w + h["u0"]])
+    assert cl == [a_left, pr["gradW"].finals[1]], "claims on A"
+    off, cl, v_mw, w_one = merge_at(off, ln + 2 * lw, [vn_f + vi_f + f["u1"], v_rw + g["u1"] + vi_a])
+    assert cl == [pr["fwd"].finals[2], w_left], "claims on W"
     assert off == len(buf)
     return dict(
-        A=[(v_ra + f["u0"] + vi_f, a_left), (vn_w + vi_w + h["u0"], pr["gradW"].finals[1])],
-        W=[(vn_f + vi_f + f["u1"], pr["fwd"].finals[2]), (v_rw + g["u1"] + vi_a, w_left)],
+        A=[(v_ma, a_one)],
+        W=[(v_mw, w_one)],
         GZ=[(v_rg + g["u0"] + vi_a, gz_left)],
         Zlast=(f["w"][:lt] + f["u0"] + f["u1"], z_last),
         GZlast=(vn_w[:lt] + vi_w + h["u1"], gz_last),

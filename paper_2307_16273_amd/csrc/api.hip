@@ -304,6 +304,16 @@ extern "C" int zkdl_transcript_digest(const zkdl_transcript* t, uint8_t host_out
 // ---------------------------------------------------------------------------
 // tensors
 // ---------------------------------------------------------------------------
+// 32 little-endian bytes below the modulus
+static bool fr_bytes_canonical(const uint8_t* le) {
+    for (int l = 7; l >= 0; --l) {
+        const uint32_t w = (uint32_t)le[4 * l] | ((uint32_t)le[4 * l + 1] << 8) | ((uint32_t)le[4 * l + 2] << 16) |
+                           ((uint32_t)le[4 * l + 3] << 24);
+        if (w != frc::MOD[l]) return w < frc::MOD[l];
+    }
+    return false;
+}
+
 static bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
 static int ilog2_u64(uint64_t x) {
     int l = 0;
@@ -1033,6 +1043,90 @@ extern "C" int reindex_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const i
 }
 
 // ---------------------------------------------------------------------------
+// several claims on one tensor -> one
+// ---------------------------------------------------------------------------
+static const uint32_t ZKMG_MAGIC = 0x474D4B5Au;
+
+// Device part shared by the entry point and the linked aggregate: K points of d coordinates each,
+// point k = the challenges from `points[k]` on (device, Montgomery form); x = the tensor as field
+// elements.  `keep` receives the work memory (to be freed once the stream has drained).
+static int enqueue_merge(zkdl_ctx* ctx, int K, const Fr* const* points, FrTab x, int d, std::vector<void*>& keep) {
+    if (ctx->n_chal + K + d > ZK_MAX_CHAL) return ZKDL_EINVAL;
+    const uint64_t n = (uint64_t)1 << d;
+    uint32_t hdr[4] = {ZKMG_MAGIC, (uint32_t)d, (uint32_t)K, 0};
+    zk_write_proof_words(ctx, hdr, 4);
+    void* mem = zk_alloc(ctx, (size_t)(K + 1) * n * 32 + zk_sumcheck_work_bytes(2, d));
+    if (!mem) return ZKDL_ENOMEM;
+    keep.push_back(mem);
+    uint32_t* w = (uint32_t*)mem;
+    BetaJob jobs[ZKDL_REINDEX_MAX_K];
+    FrTab beta[ZKDL_REINDEX_MAX_K];
+    for (int k = 0; k < K; ++k) {
+        jobs[k].point = points[k];
+        jobs[k].m = d;
+        jobs[k].out = beta[k] = make_tab(w, n);
+        w += 8 * n;
+    }
+    const FrTab P = make_tab(w, n);
+    w += 8 * n;
+    int rc = zk_build_beta_many(ctx, jobs, K);
+    if (rc == ZKDL_OK) rc = zk_merge(ctx, K, beta, x, P, d, w);
+    return rc;
+}
+
+extern "C" int claims_merge_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const zkdl_fr* const* points,
+                                  zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
+                                  zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !X || !tr || K < 1 || K > ZKDL_REINDEX_MAX_K || !is_pow2(X->numel)) return ZKDL_EINVAL;
+    const int d = ilog2_u64(X->numel);
+    if (d > 0 && !points) return ZKDL_EINVAL;
+    if (d > 30) return ZKDL_EINVAL;
+    std::vector<uint8_t> pts((size_t)(K * d > 0 ? K * d : 1) * 32);
+    for (int k = 0; k < K && d > 0; ++k) {
+        if (!points[k]) return ZKDL_EINVAL;
+        for (int i = 0; i < d; ++i)
+            if (!fr_bytes_canonical(points[k][i].le)) return ZKDL_EINVAL;
+        memcpy(pts.data() + (size_t)k * d * 32, points[k], (size_t)d * 32);
+    }
+    HostSha hs;
+    hs.u32((uint32_t)d);
+    hs.u32((uint32_t)K);
+    hs.bytes(pts.data(), (size_t)K * d * 32);
+    uint8_t dg[32];
+    ts::digest(hs.s, dg);
+    uint32_t dgw[8];
+    for (int i = 0; i < 8; ++i)
+        dgw[i] = (uint32_t)dg[4 * i] | ((uint32_t)dg[4 * i + 1] << 8) | ((uint32_t)dg[4 * i + 2] << 16) |
+                 ((uint32_t)dg[4 * i + 3] << 24);
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    zk_absorb_words(ctx, "merge", dgw, 8);
+    void* d_pts = nullptr;
+    Fr* pm = (Fr*)zk_alloc(ctx, pts.size());
+    FrView view;
+    view.scratch = nullptr;
+    std::vector<void*> keep;
+    rc = pm ? upload_bytes(ctx, pts.data(), (size_t)K * d * 32, &d_pts) : ZKDL_ENOMEM;
+    if (rc == ZKDL_OK) rc = as_fr(ctx, X, &view);
+    if (rc == ZKDL_OK) {
+        zk_launch_points_to_mont(ctx, (const uint8_t*)d_pts, K * d, pm);
+        const Fr* pk[ZKDL_REINDEX_MAX_K];
+        for (int k = 0; k < K; ++k) pk[k] = pm + (size_t)k * d;
+        rc = enqueue_merge(ctx, K, pk, view.tab, d, keep);
+    }
+    int ids[ZKDL_REINDEX_MAX_K + 2];
+    for (int k = 0; k < K; ++k) ids[k] = 8 + k;
+    ids[K] = 0;
+    ids[K + 1] = 1;
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, K + 2, claims);
+    for (void* p : keep) zk_free(ctx, p);
+    zk_free(ctx, view.scratch);
+    zk_free(ctx, pm);
+    zk_free(ctx, d_pts);
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
+// ---------------------------------------------------------------------------
 // zkReLU and the aggregated proof
 // ---------------------------------------------------------------------------
 static int stage_ints(zkdl_ctx* ctx, const int64_t* host, uint64_t n, void** dev_out) {
@@ -1065,16 +1159,6 @@ static int enqueue_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga
     uint32_t hdr[8] = {ZKRL_MAGIC, hw[0], hw[1], hw[2], hw[3], hw[4], 0, 0};
     zk_write_proof_words(ctx, hdr, 8);
     return zk_zkrelu(ctx, z_dev, ga_dev, D, Q, R, mode != 0);
-}
-
-// 32 little-endian bytes below the modulus
-static bool fr_bytes_canonical(const uint8_t* le) {
-    for (int l = 7; l >= 0; --l) {
-        const uint32_t w = (uint32_t)le[4 * l] | ((uint32_t)le[4 * l + 1] << 8) | ((uint32_t)le[4 * l + 2] << 16) |
-                           ((uint32_t)le[4 * l + 3] << 24);
-        if (w != frc::MOD[l]) return w < frc::MOD[l];
-    }
-    return false;
 }
 
 static int zkrelu_call(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint64_t D, int Q, int R,
@@ -1303,7 +1387,9 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
     if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tA, &tG, 1, 0, 0, 16, nullptr);
     const int f_u0 = cf + ln, f_vn = cf + ln + lb + lw, f_vi = f_vn + ln;
     const int a_u0 = ca + ln, a_u1 = a_u0 + lb, a_vn = ca + ln + lb + lw, a_vi = a_vn + ln;
-    const int w_u1 = cw + ln + lw, w_vn = cw + ln + lw + lw, w_vi = w_vn + ln;
+    const int w_u0 = cw + ln, w_u1 = cw + ln + lw, w_vn = cw + ln + lw + lw, w_vi = w_vn + ln;
+    const int f_u1 = f_u0 + lb;
+    int ri_a_v = 0, ri_w_v = 0;   // first round challenge of the re-indexing sumchecks on A and W
     std::vector<void*> keep;
     if (rc == ZKDL_OK) {
         // zkReLU at the points the three families have left: u_Z = point of forward's claim_0,
@@ -1331,6 +1417,7 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
             ChalIdx u = {};
             for (int i = 0; i < lb; ++i) u.v[i] = (int16_t)(f_u0 + i);
             for (int i = 0; i < lw; ++i) u.v[lb + i] = (int16_t)(f_vi + i);
+            ri_a_v = ctx->n_chal + 2;   // its two coefficients come first, then the ln rounds
             rc = enqueue_reindex_linked(ctx, w->A, N, w->B, w->width, maps_a, pts, u, keep);
         }
         // G_Z: gradA's first final is an evaluation of the shifted stack, u = (u0, v_i)
@@ -1347,7 +1434,47 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
             ChalIdx u = {};
             for (int i = 0; i < lw; ++i) u.v[i] = (int16_t)(a_u1 + i);
             for (int i = 0; i < lw; ++i) u.v[lw + i] = (int16_t)(a_vi + i);
+            ri_w_v = ctx->n_chal + 1;
             rc = enqueue_reindex_linked(ctx, w->W, N, w->width, w->width, maps_down, pts, u, keep);
+        }
+    }
+    // the two claims on A (re-indexing's, gradW's final on A^T) and on W (forward's final,
+    // re-indexing's) become one each
+    auto merge2 = [&](const int32_t* X, int d, const ChalIdx& p0, const ChalIdx& p1) -> int {
+        if (d > ZK_CHAL_SET_MAX / 2) return ZKDL_EINVAL;
+        const int at0 = ZK_MAX_CHAL - ZK_CHAL_SET_MAX, at1 = at0 + ZK_CHAL_SET_MAX / 2;
+        if (ctx->n_chal + 2 + d > at0) return ZKDL_EINVAL;
+        uint32_t hw2[2] = {(uint32_t)d, 2};
+        zk_absorb_words(ctx, "merge", hw2, 2);
+        zk_launch_chal_set(ctx, at0, d, nullptr, &p0);
+        zk_launch_chal_set(ctx, at1, d, nullptr, &p1);
+        const uint64_t n = (uint64_t)1 << d;
+        void* xf = zk_alloc(ctx, n * 32);
+        if (!xf) return ZKDL_ENOMEM;
+        keep.push_back(xf);
+        const FrTab x = make_tab(xf, n);
+        zk_launch_convert(ctx, X, TK_I32, n, x);
+        const Fr* pk[2] = {ctx->dev->chal + at0, ctx->dev->chal + at1};
+        return enqueue_merge(ctx, 2, pk, x, d, keep);
+    };
+    // the re-indexing sumchecks' own challenges: K coefficients, then ln rounds
+    if (rc == ZKDL_OK) {
+        ChalIdx p0 = {}, p1 = {};
+        int at = 0;
+        auto put = [&](ChalIdx& p, int from, int count) {
+            for (int i = 0; i < count; ++i) p.v[at++] = (int16_t)(from + i);
+        };
+        put(p0, ri_a_v, ln), put(p0, f_u0, lb), put(p0, f_vi, lw);
+        at = 0;
+        put(p1, w_vn, ln), put(p1, w_vi, lb), put(p1, w_u0, lw);
+        rc = merge2(w->A, li, p0, p1);
+        if (rc == ZKDL_OK) {
+            ChalIdx q0 = {}, q1 = {};
+            at = 0;
+            put(q0, f_vn, ln), put(q0, f_vi, lw), put(q0, f_u1, lw);
+            at = 0;
+            put(q1, ri_w_v, ln), put(q1, a_u1, lw), put(q1, a_vi, lw);
+            rc = merge2(w->W, ln + 2 * lw, q0, q1);
         }
     }
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);

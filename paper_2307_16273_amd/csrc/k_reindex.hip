@@ -74,3 +74,72 @@ int zk_reindex(zkdl_ctx* ctx, const ReindexJob& job, FrTab t, FrTab p, int ln, v
     FrTab src[2] = {p, t};
     return zk_sumcheck_product(ctx, 2, src, work_mem, ln, 0);
 }
+
+// ---------------------------------------------------------------------------
+// Several claims on one tensor -> one: sum_k r_k X~(p_k) = sum_b P[b] X(b) with
+// P = sum_k r_k beta~(p_k, .), the defining sum of the multilinear extension (Sec. 2.2) taken
+// for K points at once; Eq. sc-reindex with every sub-stack the stack itself and the sum over
+// all variables.  Protocol zkdl opens one evaluation per stack: this produces it.
+// ---------------------------------------------------------------------------
+struct MgTabs {
+    FrTab beta[ZKDL_REINDEX_MAX_K];   // beta~(p_k, .), n entries each
+};
+
+// part[k * gridDim.x + block] = the block's share of sum_b beta_k[b] X[b]
+__global__ __launch_bounds__(ZK_BLOCK) void k_mg_claims_part(MgTabs m, int K, FrTab x, uint64_t n, Fr* part) {
+    __shared__ uint32_t red[64];
+    for (int k = 0; k < K; ++k) {
+        Fr acc = fr_zero();
+        for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < n; b += (uint64_t)gridDim.x * blockDim.x)
+            acc = fr_add(acc, fr_mul(tab_ld(m.beta[k], b), tab_ld(x, b)));
+        acc = block_sum(acc, red);
+        if (threadIdx.x == 0) part[(size_t)k * gridDim.x + blockIdx.x] = acc;
+        __syncthreads();
+    }
+}
+
+// block k: claim_k = sum of its nblk partial sums -> st->scal[scal_base + k]
+__global__ __launch_bounds__(ZK_BLOCK) void k_mg_claims_sum(DevState* st, const Fr* part, int nblk, int scal_base) {
+    __shared__ uint32_t red[64];
+    const int k = blockIdx.x;
+    Fr acc = fr_zero();
+    for (int i = threadIdx.x; i < nblk; i += blockDim.x) acc = fr_add(acc, part[(size_t)k * nblk + i]);
+    acc = block_sum(acc, red);
+    if (threadIdx.x == 0) st->scal[scal_base + k] = acc;
+}
+
+// P[b] = sum_k r_k beta_k[b], r_k = chal[chal_base + k]
+__global__ __launch_bounds__(ZK_BLOCK) void k_mg_weights(const DevState* st, MgTabs m, int K, int chal_base,
+                                                         uint64_t n, FrTab p) {
+    __shared__ Fr r[ZKDL_REINDEX_MAX_K];
+    if (threadIdx.x < K) r[threadIdx.x] = st->chal[chal_base + threadIdx.x];
+    __syncthreads();
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < n; b += (uint64_t)gridDim.x * blockDim.x) {
+        Fr acc = fr_mul(r[0], tab_ld(m.beta[0], b));
+        for (int k = 1; k < K; ++k) acc = fr_add(acc, fr_mul(r[k], tab_ld(m.beta[k], b)));
+        tab_st(p, b, acc);
+    }
+}
+
+int zk_merge(zkdl_ctx* ctx, int K, const FrTab* beta, FrTab x, FrTab p, int d, void* work_mem) {
+    MgTabs m;
+    for (int k = 0; k < ZKDL_REINDEX_MAX_K; ++k) m.beta[k] = k < K ? beta[k] : make_tab(nullptr, 0);
+    const uint64_t n = (uint64_t)1 << d;
+    const int claims_scal = 8;
+    uint64_t blocks = (n + ZK_BLOCK - 1) / ZK_BLOCK;
+    const unsigned nblk = (unsigned)(blocks < (uint64_t)ZK_MAX_PART_BLOCKS ? blocks : (uint64_t)ZK_MAX_PART_BLOCKS);
+    zk_flush_frames(ctx);
+    // ctx->partials holds ZK_MAX_PART_BLOCKS * ZK_MAX_EVALS * 2 elements >= K * nblk for K <= 8
+    hipLaunchKernelGGL(k_mg_claims_part, dim3(nblk), dim3(ZK_BLOCK), 0, ctx->stream, m, K, x, n, ctx->partials);
+    hipLaunchKernelGGL(k_mg_claims_sum, dim3(K), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev,
+                       (const Fr*)ctx->partials, (int)nblk, claims_scal);
+    const int chal_base = ctx->n_chal;
+    hipLaunchKernelGGL(k_ri_absorb, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, claims_scal, K,
+                       (uint32_t)ctx->proof_len, chal_base);
+    ctx->proof_len += 32 * (size_t)K;
+    ctx->n_chal += K;
+    const unsigned wblk = (unsigned)(blocks < 4096 ? blocks : 4096);
+    hipLaunchKernelGGL(k_mg_weights, dim3(wblk), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, m, K, chal_base, n, p);
+    FrTab src[2] = {p, x};
+    return zk_sumcheck_product(ctx, 2, src, work_mem, d, 0);
+}

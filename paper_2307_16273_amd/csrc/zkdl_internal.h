@@ -168,6 +168,11 @@ struct ReindexJob {
 // P built into p; product sumcheck on (p, t) over ln variables, finals at scal[0], scal[1]
 int zk_reindex(zkdl_ctx* ctx, const ReindexJob& job, FrTab t, FrTab p, int ln, void* work_mem);
 
+// K claims X~(p_k) on the table x (2^d entries) -> one: the claims -> scal[8 ..), absorbed and written
+// to the proof; K coefficients drawn; P = sum_k r_k beta[k] built into p; product sumcheck on (p, x),
+// finals at scal[0], scal[1]
+int zk_merge(zkdl_ctx* ctx, int K, const FrTab* beta, FrTab x, FrTab p, int d, void* work_mem);
+
 // ---- k_zkrelu.hip ----------------------------------------------------------------
 // optimized aggregated matrix-product protocol: stack rounds with f_t, then the single-product sumcheck
 int zk_matmul_ft(zkdl_ctx* ctx, const FrTab* src, void* work_mem, int ln, int l2, const FrTab* wsuf, int w_idx,

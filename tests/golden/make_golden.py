@@ -119,13 +119,25 @@ def reindex_case():
             "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
 
 
+def merge_case():
+    """Three claims on one tensor of 16 elements merged into one (Sec. 2.2; Eq. sc-reindex over all variables)."""
+    rng = np.random.default_rng(20230720)
+    x = rng.integers(-50, 50, 16).astype(np.int64)
+    pts = [uniform_fr_limbs(rng, 4).tobytes() for _ in range(3)]
+    ts = Transcript(14)
+    buf, info = P.merge_prove(fr_array(x), [list(fr_array_from_le(p, 4)) for p in pts], ts)
+    return {"protocol": "claims_merge_prove", "cite": "Sec. 2.2, Eq. sc-reindex, Protocol zkdl", "seed": 14,
+            "x": x.tolist(), "points_le_hex": [p.hex() for p in pts],
+            "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
+
+
 if __name__ == "__main__":
     for name, fn in (("product_k3_d3", product_case), ("matmul_n2_2x4x2", matmul_case),
                      ("matmul_ft_n2_2x4x2", matmul_ft_case),
                      ("zkrelu_d4_q5_r3", zkrelu_case), ("zkrelu_at_d4_q5_r3", zkrelu_at_case),
                      ("aggregate_l2_w4_b2_t2", aggregate_case),
                      ("aggregate_linked_l2_w4_b2_t2", aggregate_linked_case),
-                     ("reindex_n4_d8_k2", reindex_case)):
+                     ("reindex_n4_d8_k2", reindex_case), ("merge_d4_k3", merge_case)):
         with open(os.path.join(HERE, name + ".json"), "w") as f:
             json.dump(fn(), f, indent=1)
             f.write("\n")

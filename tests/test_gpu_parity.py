@@ -246,6 +246,58 @@ def test_reindex_prove(lib, ctx, n, d, case, kind):
     assert xw == got["claims"][-1]
 
 
+@pytest.mark.parametrize("shape,k,kind", [((8,), 2, "fr"), ((1,), 2, "fr"), ((4, 64), 3, "i32"), ((2, 8, 16), 1, "i64"),
+                                          ((16, 4096), 2, "i32"), ((2, 1024, 1024), 2, "i32"), ((3000 // 3000 * 4096,), 8, "fr")])
+def test_claims_merge(lib, ctx, shape, k, kind):
+    """K claims on one tensor become one: proof bytes, claims, challenges and transcript agree."""
+    import torch
+    n = int(np.prod(shape))
+    d = n.bit_length() - 1
+    say(f"claims_merge shape={shape} K={k} {kind}")
+    rng = np.random.default_rng(n + k)
+    pts = [fr_array_from_le(rand_fr_bytes(70 + j, d), d).tolist() if d else [] for j in range(k)]
+    if kind == "fr":
+        raw = rand_fr_bytes(n + 1, n)
+        x = lib.fr_tensor_upload(ctx, raw, shape)
+        xo = fr_array_from_le(raw, n)
+    else:
+        dt = np.int32 if kind == "i32" else np.int64
+        vals = rng.integers(-2 ** 31, 2 ** 31, n).astype(dt)
+        x = lib.tensor_wrap_int(ctx, torch.from_numpy(vals).cuda(), shape)
+        xo = None
+    tr = lib.Transcript(35)
+    got = lib.claims_merge_prove(ctx, x, pts, tr)
+    if n <= 1 << 16:
+        if xo is None:
+            xo = fr_array(vals)
+        ots = OracleTranscript(35)
+        buf, info = P.merge_prove(xo, pts, ots)
+        assert got["proof"] == buf
+        assert got["points"] == ots.challenges
+        assert got["claims"][:k] == info["claims"] and got["claims"][k + 1] == info["inner"].finals[1]
+        assert tr.digest() == ots.digest()
+    else:
+        # too large for the oracle's prover: its verifier replays the proof, and the claims are
+        # evaluated from the integers one stack slot at a time
+        ots = OracleTranscript(35)
+        claims, vs, left = P.merge_verify(got["proof"], d, pts, ots)
+        assert tr.digest() == ots.digest() and got["points"] == ots.challenges
+        st = vals.reshape(shape)
+        for c, pt in zip(claims + [left], pts + [vs]):
+            assert c == _stack_mle(st, pt[:1], pt[1:11], pt[11:])
+
+
+def test_claims_merge_rejects_bad_arguments(lib, ctx):
+    say("claims_merge bad arguments")
+    x = lib.fr_tensor_upload(ctx, rand_fr_bytes(1, 8), (8,))
+    tr = lib.Transcript(1)
+    before = tr.digest()
+    for pts in ([[0, 0, R_MOD]], [[0, 0, 0]] * 9, []):
+        with pytest.raises(lib.ZkdlError):
+            lib.claims_merge_prove(ctx, x, pts, tr)
+    assert tr.digest() == before
+
+
 def test_reindex_prove_rejects_bad_arguments(lib, ctx):
     say("reindex_prove argument checks")
     x = lib.fr_tensor_upload(ctx, np.arange(8, dtype=np.int64), (4, 2))

@@ -266,3 +266,45 @@ def test_reindex_verifier_rejects_tampering_and_wrong_maps():
             assert claims == info["claims"] and xw == info["inner"].finals[1]
     with pytest.raises(AssertionError):
         P.reindex_verify(buf, n, d, [[0, 1, 2, 3], [1, 2, 3, 0]], points, u, Transcript(4))
+
+
+@pytest.mark.parametrize("d,k", [(3, 2), (4, 3), (0, 2), (5, 1)])
+def test_merge_against_definitions(d, k):
+    """Several claims on one tensor become one: the claims are MLE evaluations, the combined
+    claim is the plain sum over the cube of P[b] X(b), the claim left is X~(v)."""
+    rng = np.random.default_rng(400 + 10 * d + k)
+    x = fr_array(rng.integers(-1000, 1000, 1 << d))
+    pts = [[int.from_bytes(rng.bytes(40), "little") % R_MOD for _ in range(d)] for _ in range(k)]
+    ts = Transcript(15)
+    buf, info = P.merge_prove(x, pts, ts)
+    assert info["claims"] == [mle_eval(x, pt) for pt in pts]
+    weights = [sum(r * int(beta_table(pt)[b]) for r, pt in zip(info["r"], pts)) % R_MOD for b in range(1 << d)]
+    assert info["inner"].claim0 == sum(w * int(v) for w, v in zip(weights, x)) % R_MOD
+    tv = Transcript(15)
+    claims, vs, left = P.merge_verify(buf, d, pts, tv)
+    assert tv.digest() == ts.digest() and claims == info["claims"]
+    assert left == mle_eval(x, vs)
+    # inside a larger proof the header is short and the transcript differs
+    buf2, _ = P.merge_prove(x, pts, Transcript(15), bind_statement=False)
+    assert buf2[:16] == buf[:16] and (d == 0 or buf2 != buf)
+    P.merge_verify(buf2, d, pts, Transcript(15), bind_statement=False)
+
+
+def test_merge_verifier_rejects_tampering_and_wrong_points():
+    rng = np.random.default_rng(77)
+    d = 3
+    x = fr_array(rng.integers(-50, 50, 8))
+    pts = [[int.from_bytes(rng.bytes(40), "little") % R_MOD for _ in range(d)] for _ in range(2)]
+    buf, _ = P.merge_prove(x, pts, Transcript(16))
+    P.merge_verify(buf, d, pts, Transcript(16))
+    for off in list(range(16, len(buf), 37)) + [len(buf) - 1]:
+        bad = bytearray(buf)
+        bad[off] ^= 1
+        with pytest.raises(AssertionError):
+            P.merge_verify(bytes(bad), d, pts, Transcript(16))
+    for bind in (True, False):
+        b2, _ = P.merge_prove(x, pts, Transcript(16), bind_statement=bind)
+        other = [list(pts[0]), list(pts[1])]
+        other[1][2] = (other[1][2] + 1) % R_MOD
+        with pytest.raises(AssertionError):
+            P.merge_verify(b2, d, other, Transcript(16), bind_statement=bind)
