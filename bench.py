@@ -220,6 +220,8 @@ def main():
             out["config"]["proof_ms_" + key] = 1e3 * med
             if st > 1:
                 out["config"]["proof_ms_" + key + "_per_step"] = 1e3 * med / st
+            med, _ = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + cfg), linked=True), 3)
+            out["config"]["proof_ms_" + key + "_linked"] = 1e3 * med
             del dw, wit
             ctx.trim()
     if not args.no_cpu_baseline:

@@ -768,3 +768,18 @@ def test_large_aggregates_by_properties(lib, ctx, name, layers, width, batch, st
     assert tr.digest() == ots.digest()
     assert got["points"] == ots.challenges
     ctx.trim()
+    # the same window with the claims chained: every link holds, and the one claim left on each of
+    # A, G_Z and W (the merge on W runs over the whole stack, 2^26 or 2^27 elements) is the MLE of
+    # the witness stack
+    say(name + " (linked)")
+    tr = lib.Transcript(CONFIG_SEED + cfg + 1)
+    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr, linked=True)
+    ots = OracleTranscript(CONFIG_SEED + cfg + 1)
+    left = P.aggregate_linked_verify(got["proof"], ots)
+    assert tr.digest() == ots.digest()
+    ln, lb, lw = (layers * steps).bit_length() - 1, batch.bit_length() - 1, width.bit_length() - 1
+    for nm in ("A", "GZ", "W"):
+        rows_bits = lb if nm != "W" else lw
+        (point, value), = left[nm]
+        assert value == _stack_mle(wit[nm], point[:ln], point[ln:ln + rows_bits], point[ln + rows_bits:]), nm
+    ctx.trim()
