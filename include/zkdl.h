@@ -228,6 +228,25 @@ int claims_merge_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const zkdl_fr
                        zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
                        zkdl_fr* points_out, size_t* npoints);
 
+/* claims_merge_stack_prove: the same statement for a stack X [N, ...] (D = numel / N) on tables
+ * of D, not N D, entries.  Claim k is X~(s_k, q_k), its point = s_k over the stack axis followed
+ * by q_k over the rest.  With T[k, x] = X~(s_k, x) and E[k, x] = r_k beta~(q_k, x) (k padded
+ * with zero rows to a power of two),
+ *   sum_k r_k X~(s_k, q_k) = sum_{k, x} E[k, x] T[k, x]:
+ * a product sumcheck over (k, x), k leading, with challenges (rho, v), leaves
+ * T~(rho, v) = sum_k beta~(rho, k) X~(s_k, v), claims with one common inner point, and Eq.
+ * sc-reindex, T~(rho, v) = sum_i Pn[i] X~(i, v), Pn[i] = sum_k beta~(rho, k) beta~(s_k, i), a
+ * product sumcheck over i, leaves X~(v_n, v).  The verifier computes E~(rho, v), Pn~(v_n) and
+ * checks that the second sumcheck starts from the first one's final on T.
+ * A 3-d (or higher) tensor is taken as [N, rows, cols...]: X~(i, v) is evaluated columns
+ * first.  claims (host, K + 2, may be NULL): the K claims, Pn~(v_n), X~(v_n, v).
+ * Transcript: "merge_stack" with the SHA-256 digest of u32le N, D, K and the points' bytes;
+ * "c" the K claims; one draw of K; the two product sumchecks, each with its claim_0.
+ * Proof: "ZKMS", N, D, K, the K claims, two SC blocks.  Errors as claims_merge_prove. */
+int claims_merge_stack_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const zkdl_fr* const* points,
+                             zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
+                             zkdl_fr* points_out, size_t* npoints);
+
 /* zkrelu_prove: the combined sumcheck of App. A over aux in {0,1}^{2 x D x (Q+R)}
  * (bit axis padded to a power of two), weights r^2, r, 1, r'r^2, r'r, r', then the
  * merge of the three claims on aux into one.  Z, GA: D signed (Q+R)-bit
@@ -290,13 +309,12 @@ int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* 
  *  4. re-indexing on G_Z and on W with that shifted sub-stack alone, at gradA's stack point,
  *     common points (u0, v_i) and (u1, v_i);
  *  5. the two claims standing on A (from 3, and gradW's final on A^T) merged into one as in
- *     claims_merge_prove, then the two on W (forward's final, and the one from 4).
- * One claim per stack is left.  The re-indexing headers carry N, D, K only, the merge headers
- * d, K only.  What the verifier checks between the parts
+ *     claims_merge_stack_prove, then the two on W (forward's final, and the one from 4).
+ * One claim per stack is left.  The re-indexing and merge headers carry N, D, K only.  What the verifier checks between the parts
  * (c_GA = gradA's claim_0; forward's claim_0 - c_Z and gradW's final on G_Z - c_GZ are the
  * last layer's share; the sub-stack claims equal the finals and c_A) needs nothing from the
  * prover.  Proof: "ZKAL" header (L, B, width, T, Q, R, 0), three SC blocks, the zkReLU
- * proof, three "ZKRI" proofs, two "ZKMG" proofs.  points_out: every challenge in order; the 4 log2(N B width)
+ * proof, three "ZKRI" proofs, two "ZKMS" proofs.  points_out: every challenge in order; the 4 log2(N B width)
  * coordinates given to zkReLU are repeated in front of its own draws. */
 int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
                            size_t* proof_len, zkdl_fr* points_out, size_t* npoints);

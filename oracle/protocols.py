@@ -353,6 +353,104 @@ def merge_verify(buf, d, points, ts, bind_statement=True):
     return claims, vs, xw
 
 
+MS_MAGIC = 0x534D4B5A   # "ZKMS"
+
+
+def _stack_merge_header(ts, n, d, points, bind_statement):
+    if bind_statement:
+        import hashlib
+        h = hashlib.sha256(struct.pack("<III", n, d, len(points)))
+        for pt in points:
+            h.update(b"".join(to_le(x) for x in pt))
+        ts.absorb(b"merge_stack", h.digest())
+    else:
+        ts.absorb_u32(b"merge_stack", [n, d, len(points)])
+
+
+def _stack_merge_tables(k_sub, r, inner_points, t_rows, d):
+    """The two tables of the inner sumcheck, the claim index k as the leading variables:
+    E[k, x] = r_k beta~(q_k, x), T[k, x] = X~(s_k, x); zero rows up to a power of two."""
+    k_pad = 1 << max(0, (k_sub - 1).bit_length())
+    e = np.zeros(k_pad * d, dtype=object)
+    t = np.zeros(k_pad * d, dtype=object)
+    for k in range(k_sub):
+        e[k * d:(k + 1) * d] = (r[k] * beta_table(inner_points[k])) % R_MOD
+        t[k * d:(k + 1) * d] = t_rows[k]
+    return e, t, ilog2(k_pad)
+
+
+def stack_merge_prove(x, n, d, points, ts, bind_statement=True):
+    """merge_prove's statement for a stack X [N, D] at the cost of tables of D (not N D)
+    entries: K claims X~(s_k, q_k), s_k over the stack axis, q_k over the rest.
+    1. The prover binds the stack axis of every claim: T_k(x) = X~(s_k, x).
+    2. With coefficients r_k,  sum_k r_k X~(s_k, q_k) = sum_{k, x} E[k, x] T[k, x]  (tables of
+       _stack_merge_tables): one product sumcheck over (k, x), challenges (rho, v).  It leaves
+       T~(rho, v) = sum_k beta~(rho, k) X~(s_k, v), a combination of claims with the common
+       point v over the inner dimensions, which is the left-hand side of Eq. sc-reindex with
+       the sub-stacks the stack itself and the coefficients beta~(rho, k).
+    3. Eq. sc-reindex: T~(rho, v) = sum_i Pn[i] X~(i, v), Pn[i] = sum_k beta~(rho, k) beta~(s_k, i):
+       a product sumcheck over i leaves the one claim X~(v_n, v).
+    The verifier computes E~(rho, v) = sum_k beta~(rho, k) r_k beta~(q_k, v) and
+    Pn~(v_n) = sum_k beta~(rho, k) beta~(s_k, v_n), and checks that the second sumcheck starts
+    from the first one's final on T.
+    Transcript: "merge_stack" (digest of N, D, K and the points; inside a larger proof the
+    three words N, D, K); "c" the K claims; draw K; the two product sumchecks one after the
+    other (each absorbs its claim_0).  Proof: "ZKMS", N, D, K, the K claims, two SC blocks."""
+    ln, ld = ilog2(n), ilog2(d)
+    k_sub = len(points)
+    assert 1 <= k_sub <= 8 and all(len(pt) == ln + ld for pt in points)
+    _stack_merge_header(ts, n, d, points, bind_statement)
+    t_rows = [[int(v) for v in partial_eval(x, [1, n, d], 1, 2, pt[:ln])[0]] for pt in points]
+    claims = [mle_eval(np.array(t, dtype=object), pt[ln:]) for t, pt in zip(t_rows, points)]
+    ts.absorb_fr(b"c", claims)
+    r = ts.challenges_vec(k_sub)
+    e_tab, t_tab, lk = _stack_merge_tables(k_sub, r, [pt[ln:] for pt in points], t_rows, d)
+    inner, vs = prove([e_tab, t_tab], [(1, [0, 1])], 2, ts)
+    assert inner.claim0 == sum(rk * ck for rk, ck in zip(r, claims)) % R_MOD
+    rho, v = vs[:lk], vs[lk:]
+    b_rho = beta_table(rho)
+    pn = np.zeros(n, dtype=object)
+    for k, pt in enumerate(points):
+        pn = (pn + int(b_rho[k]) * beta_table(pt[:ln])) % R_MOD
+    tn, _ = partial_eval(x, [n, d], 1, 2, v)
+    outer, vn = prove([pn, np.asarray(tn, dtype=object)], [(1, [0, 1])], 2, ts)
+    assert outer.claim0 == inner.finals[1]
+    out = ([struct.pack("<IIII", MS_MAGIC, n, d, k_sub)] + [to_le(c) for c in claims]
+           + [inner.to_bytes(), outer.to_bytes()])
+    return b"".join(out), dict(claims=claims, r=r, rho=rho, v=v, vn=vn, inner=inner, outer=outer)
+
+
+def stack_merge_verify(buf, n, d, points, ts, bind_statement=True):
+    """Returns (the K claims, the point (v_n, v), the remaining claim X~(v_n, v))."""
+    magic, n_, d_, k_sub = struct.unpack_from("<IIII", buf, 0)
+    assert magic == MS_MAGIC and n_ == n and d_ == d and k_sub == len(points)
+    ln, ld = ilog2(n), ilog2(d)
+    lk = max(0, (k_sub - 1).bit_length())
+    _stack_merge_header(ts, n, d, points, bind_statement)
+    claims = [from_le(buf[16 + 32 * k:48 + 32 * k]) for k in range(k_sub)]
+    ts.absorb_fr(b"c", claims)
+    r = ts.challenges_vec(k_sub)
+    inner, off = SumcheckProof.from_bytes(buf, 16 + 32 * k_sub)
+    outer, end = SumcheckProof.from_bytes(buf, off)
+    assert end == len(buf)
+    assert inner.n_finals == 2 and inner.degree == 2 and len(inner.rounds) == lk + ld
+    assert outer.n_finals == 2 and outer.degree == 2 and len(outer.rounds) == ln
+    expect0 = sum(rk * ck for rk, ck in zip(r, claims)) % R_MOD
+    last, vs = verify_rounds(inner, ts, expected_claim0=expect0)
+    rho, v = vs[:lk], vs[lk:]
+    ef, tf = inner.finals
+    assert ef * tf % R_MOD == last, "inner final claim mismatch"
+    b_rho = beta_table(rho)
+    assert ef == sum(int(b_rho[k]) * r[k] % R_MOD * beta_point(points[k][ln:], v)
+                     for k in range(k_sub)) % R_MOD, "E~(rho, v) mismatch"
+    last2, vn = verify_rounds(outer, ts, expected_claim0=tf)
+    pf, xf = outer.finals
+    assert pf * xf % R_MOD == last2, "outer final claim mismatch"
+    assert pf == sum(int(b_rho[k]) * beta_point(points[k][:ln], vn) for k in range(k_sub)) % R_MOD, \
+        "Pn~(v_n) mismatch"
+    return claims, vn + v, xf
+
+
 # --------------------------------------------------------------------------
 # batched Hadamard product (Eq. exm-hadamard-batched)
 # --------------------------------------------------------------------------
@@ -711,10 +809,10 @@ def aggregate_linked_prove(wit, ts):
     4. Re-indexing on G_Z and on W, one shifted sub-stack each: gradA's finals (they are
        evaluations of the stacks of the next layer's G_Z and W) become claims on the stacks.
     5. The two claims now standing on A (from 3 and gradW's final on A^T) are merged into one,
-       and so are the two on W (forward's final and the one from 4): merge_prove.
+       and so are the two on W (forward's final and the one from 4): stack_merge_prove.
     One claim per stack is left (Protocol zkdl opens one evaluation per stack).
     Proof: "ZKAL" header, the three SC blocks, the zkReLU proof, the three ZKRI proofs, the
-    two ZKMG proofs."""
+    two ZKMS proofs."""
     n_layers, bsz, width, steps = wit["L"], wit["B"], wit["width"], wit["T"]
     q, r_bits = wit["Q"], wit["R"]
     n = n_layers * steps
@@ -763,14 +861,14 @@ def aggregate_linked_prove(wit, ts):
     assert infos["reindex_W"]["claims"] == [proofs["gradA"].finals[2]]
     parts.append(buf)
     vn_w, vi_w = h["v"][:ln], h["v"][ln:]
-    buf, infos["merge_A"] = merge_prove(fr_array(a.reshape(-1)),
-                                        [infos["reindex_A"]["v"] + f["u0"] + vi_f, vn_w + vi_w + h["u0"]],
-                                        ts, bind_statement=False)
+    buf, infos["merge_A"] = stack_merge_prove(fr_array(a.reshape(-1)), n, bsz * width,
+                                              [infos["reindex_A"]["v"] + f["u0"] + vi_f, vn_w + vi_w + h["u0"]],
+                                              ts, bind_statement=False)
     assert infos["merge_A"]["claims"] == [infos["reindex_A"]["inner"].finals[1], proofs["gradW"].finals[1]]
     parts.append(buf)
-    buf, infos["merge_W"] = merge_prove(fr_array(w.reshape(-1)),
-                                        [vn_f + vi_f + f["u1"], infos["reindex_W"]["v"] + g["u1"] + vi_a],
-                                        ts, bind_statement=False)
+    buf, infos["merge_W"] = stack_merge_prove(fr_array(w.reshape(-1)), n, width * width,
+                                              [vn_f + vi_f + f["u1"], infos["reindex_W"]["v"] + g["u1"] + vi_a],
+                                              ts, bind_statement=False)
     assert infos["merge_W"]["claims"] == [proofs["fwd"].finals[2], infos["reindex_W"]["inner"].finals[1]]
     parts.append(buf)
     return b"".join(parts), infos
@@ -825,13 +923,13 @@ def aggregate_linked_verify(buf, ts):
     assert cl == [pr["gradA"].finals[2]], "W link"
 
     def merge_at(off, d, points):
-        _, end = SumcheckProof.from_bytes(buf, off + 16 + 32 * len(points))
-        claims, vs, left = merge_verify(buf[off:end], d, points, ts, bind_statement=False)
+        _, mid = SumcheckProof.from_bytes(buf, off + 16 + 32 * len(points))
+        _, end = SumcheckProof.from_bytes(buf, mid)
+        claims, vs, left = stack_merge_verify(buf[off:end], n, d, points, ts, bind_statement=False)
         return end, claims, vs, left
-    lb, lw = ilog2(bsz), ilog2(width)
-    off, cl, v_ma, a_one = merge_at(off, ln + lb + lw, [v_ra + f["u0"] + vi_f, vn_w + vi_w + h["u0"]])
+    off, cl, v_ma, a_one = merge_at(off, bsz * width, [v_ra + f["u0"] + vi_f, vn_w + vi_w + h["u0"]])
     assert cl == [a_left, pr["gradW"].finals[1]], "claims on A"
-    off, cl, v_mw, w_one = merge_at(off, ln + 2 * lw, [vn_f + vi_f + f["u1"], v_rw + g["u1"] + vi_a])
+    off, cl, v_mw, w_one = merge_at(off, width * width, [vn_f + vi_f + f["u1"], v_rw + g["u1"] + vi_a])
     assert cl == [pr["fwd"].finals[2], w_left], "claims on W"
     assert off == len(buf)
     return dict(

@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = [
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
     "mle_partial_eval", "sumcheck_product", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_hadamard",
-    "reindex_prove", "claims_merge_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
+    "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read",
 ]
 
@@ -74,6 +74,7 @@ def load_library():
         "sumcheck_hadamard": [vp, vp, vp, vp, vp, psz, vp, vp, psz],
         "reindex_prove": [vp, vp, i, pp, C.POINTER(u64), pp, vp, vp, vp, psz, vp, vp, psz],
         "claims_merge_prove": [vp, vp, i, pp, vp, vp, psz, vp, vp, psz],
+        "claims_merge_stack_prove": [vp, vp, i, pp, vp, vp, psz, vp, vp, psz],
         "zkrelu_prove": [vp, vp, vp, u64, i, i, i, vp, vp, psz, vp, vp, psz],
         "zkrelu_prove_at": [vp, vp, vp, u64, i, i, i, vp, vp, vp, psz, vp, vp, psz],
         "aggregate_prove": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
@@ -346,16 +347,18 @@ def reindex_prove(ctx, x, maps, points, u, tr):
     return o.result()
 
 
-def claims_merge_prove(ctx, x, points, tr):
+def claims_merge_prove(ctx, x, points, tr, stack=False):
     """x: tensor handle (2^d elements); points: K lists of d field elements.  Returns the K claims,
-    P~(v) and X~(v) in `claims`."""
+    P~(v) and X~(v) in `claims`.  stack: x is a stack [N, ...] and the merge runs on tables of the
+    inner size (claims_merge_stack_prove)."""
     k = len(points)
+    name = "claims_merge_stack_prove" if stack else "claims_merge_prove"
     pbufs = [C.create_string_buffer(_fr_bytes(p), max(32 * len(p), 1)) for p in points]
     pt_ptrs = (C.c_void_p * k)(*[C.addressof(b) for b in pbufs])
     o = _Outputs(k + 2)
-    _check(load_library().claims_merge_prove(ctx.handle, x.handle, k, pt_ptrs, tr.handle, o.proof,
-                                             C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
-           "claims_merge_prove", ctx)
+    _check(getattr(load_library(), name)(ctx.handle, x.handle, k, pt_ptrs, tr.handle, o.proof,
+                                         C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
+           name, ctx)
     return o.result()
 
 

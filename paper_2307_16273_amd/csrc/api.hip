@@ -1126,6 +1126,68 @@ extern "C" int claims_merge_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, co
     return rc != ZKDL_OK ? rc : rc2;
 }
 
+static const uint32_t ZKMS_MAGIC = 0x534D4B5Au;
+
+extern "C" int claims_merge_stack_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const zkdl_fr* const* points,
+                                        zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
+                                        zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !X || !tr || K < 1 || K > ZKDL_REINDEX_MAX_K || X->ndim < 1 || !is_pow2(X->numel)) return ZKDL_EINVAL;
+    const uint64_t N = X->shape[0], D = X->numel / N;
+    const uint64_t rows = X->ndim >= 3 ? X->shape[1] : 1, cols = D / rows;
+    const int d = ilog2_u64(X->numel);
+    if (d > 0 && !points) return ZKDL_EINVAL;
+    if (N > ((uint64_t)1 << 29) || D > ((uint64_t)1 << 29)) return ZKDL_EINVAL;
+    std::vector<uint8_t> pts((size_t)(K * d > 0 ? K * d : 1) * 32);
+    for (int k = 0; k < K && d > 0; ++k) {
+        if (!points[k]) return ZKDL_EINVAL;
+        for (int i = 0; i < d; ++i)
+            if (!fr_bytes_canonical(points[k][i].le)) return ZKDL_EINVAL;
+        memcpy(pts.data() + (size_t)k * d * 32, points[k], (size_t)d * 32);
+    }
+    HostSha hs;
+    hs.u32((uint32_t)N);
+    hs.u32((uint32_t)D);
+    hs.u32((uint32_t)K);
+    hs.bytes(pts.data(), (size_t)K * d * 32);
+    uint8_t dg[32];
+    ts::digest(hs.s, dg);
+    uint32_t dgw[8];
+    for (int i = 0; i < 8; ++i)
+        dgw[i] = (uint32_t)dg[4 * i] | ((uint32_t)dg[4 * i + 1] << 8) | ((uint32_t)dg[4 * i + 2] << 16) |
+                 ((uint32_t)dg[4 * i + 3] << 24);
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    zk_absorb_words(ctx, "merge_stack", dgw, 8);
+    uint32_t hdr[4] = {ZKMS_MAGIC, (uint32_t)N, (uint32_t)D, (uint32_t)K};
+    zk_write_proof_words(ctx, hdr, 4);
+    void* d_pts = nullptr;
+    Fr* pm = (Fr*)zk_alloc(ctx, pts.size());
+    std::vector<void*> keep;
+    rc = pm ? upload_bytes(ctx, pts.data(), (size_t)K * d * 32, &d_pts) : ZKDL_ENOMEM;
+    FrTab xs = make_tab(X->data, X->numel);
+    if (rc == ZKDL_OK) {
+        zk_launch_points_to_mont(ctx, (const uint8_t*)d_pts, K * d, pm);
+        StackMergeJob job = {};
+        job.K = K;
+        for (int k = 0; k < K; ++k) job.point[k] = pm + (size_t)k * d;
+        job.kind = X->kind;
+        job.X = X->kind == TK_FR ? (const void*)&xs : X->data;
+        job.N = N;
+        job.rows = rows;
+        job.cols = cols;
+        rc = zk_stack_merge(ctx, job, keep);
+    }
+    int ids[ZKDL_REINDEX_MAX_K + 2];
+    for (int k = 0; k < K; ++k) ids[k] = 8 + k;
+    ids[K] = 0;
+    ids[K + 1] = 1;
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, K + 2, claims);
+    for (void* p : keep) zk_free(ctx, p);
+    zk_free(ctx, pm);
+    zk_free(ctx, d_pts);
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
 // ---------------------------------------------------------------------------
 // zkReLU and the aggregated proof
 // ---------------------------------------------------------------------------
@@ -1440,22 +1502,27 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
     }
     // the two claims on A (re-indexing's, gradW's final on A^T) and on W (forward's final,
     // re-indexing's) become one each
-    auto merge2 = [&](const int32_t* X, int d, const ChalIdx& p0, const ChalIdx& p1) -> int {
+    auto merge2 = [&](const int32_t* X, uint64_t rows, uint64_t cols, const ChalIdx& p0, const ChalIdx& p1) -> int {
+        const int d = ln + ilog2_u64(rows) + ilog2_u64(cols);
         if (d > ZK_CHAL_SET_MAX / 2) return ZKDL_EINVAL;
         const int at0 = ZK_MAX_CHAL - ZK_CHAL_SET_MAX, at1 = at0 + ZK_CHAL_SET_MAX / 2;
-        if (ctx->n_chal + 2 + d > at0) return ZKDL_EINVAL;
-        uint32_t hw2[2] = {(uint32_t)d, 2};
-        zk_absorb_words(ctx, "merge", hw2, 2);
+        if (ctx->n_chal + 2 + 1 + d > at0) return ZKDL_EINVAL;
+        uint32_t hw3[3] = {(uint32_t)N, (uint32_t)(rows * cols), 2};
+        zk_absorb_words(ctx, "merge_stack", hw3, 3);
+        uint32_t mh[4] = {ZKMS_MAGIC, hw3[0], hw3[1], 2};
+        zk_write_proof_words(ctx, mh, 4);
         zk_launch_chal_set(ctx, at0, d, nullptr, &p0);
         zk_launch_chal_set(ctx, at1, d, nullptr, &p1);
-        const uint64_t n = (uint64_t)1 << d;
-        void* xf = zk_alloc(ctx, n * 32);
-        if (!xf) return ZKDL_ENOMEM;
-        keep.push_back(xf);
-        const FrTab x = make_tab(xf, n);
-        zk_launch_convert(ctx, X, TK_I32, n, x);
-        const Fr* pk[2] = {ctx->dev->chal + at0, ctx->dev->chal + at1};
-        return enqueue_merge(ctx, 2, pk, x, d, keep);
+        StackMergeJob job = {};
+        job.K = 2;
+        job.point[0] = ctx->dev->chal + at0;
+        job.point[1] = ctx->dev->chal + at1;
+        job.kind = TK_I32;
+        job.X = X;
+        job.N = N;
+        job.rows = rows;
+        job.cols = cols;
+        return zk_stack_merge(ctx, job, keep);
     };
     // the re-indexing sumchecks' own challenges: K coefficients, then ln rounds
     if (rc == ZKDL_OK) {
@@ -1467,14 +1534,14 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
         put(p0, ri_a_v, ln), put(p0, f_u0, lb), put(p0, f_vi, lw);
         at = 0;
         put(p1, w_vn, ln), put(p1, w_vi, lb), put(p1, w_u0, lw);
-        rc = merge2(w->A, li, p0, p1);
+        rc = merge2(w->A, w->B, w->width, p0, p1);
         if (rc == ZKDL_OK) {
             ChalIdx q0 = {}, q1 = {};
             at = 0;
             put(q0, f_vn, ln), put(q0, f_vi, lw), put(q0, f_u1, lw);
             at = 0;
             put(q1, ri_w_v, ln), put(q1, a_u1, lw), put(q1, a_vi, lw);
-            rc = merge2(w->W, ln + 2 * lw, q0, q1);
+            rc = merge2(w->W, w->width, w->width, q0, q1);
         }
     }
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);

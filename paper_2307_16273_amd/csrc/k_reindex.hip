@@ -83,15 +83,16 @@ int zk_reindex(zkdl_ctx* ctx, const ReindexJob& job, FrTab t, FrTab p, int ln, v
 // ---------------------------------------------------------------------------
 struct MgTabs {
     FrTab beta[ZKDL_REINDEX_MAX_K];   // beta~(p_k, .), n entries each
+    FrTab x[ZKDL_REINDEX_MAX_K];      // the table claim k is taken on
 };
 
-// part[k * gridDim.x + block] = the block's share of sum_b beta_k[b] X[b]
-__global__ __launch_bounds__(ZK_BLOCK) void k_mg_claims_part(MgTabs m, int K, FrTab x, uint64_t n, Fr* part) {
+// part[k * gridDim.x + block] = the block's share of sum_b beta_k[b] x_k[b]
+__global__ __launch_bounds__(ZK_BLOCK) void k_mg_claims_part(MgTabs m, int K, uint64_t n, Fr* part) {
     __shared__ uint32_t red[64];
     for (int k = 0; k < K; ++k) {
         Fr acc = fr_zero();
         for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < n; b += (uint64_t)gridDim.x * blockDim.x)
-            acc = fr_add(acc, fr_mul(tab_ld(m.beta[k], b), tab_ld(x, b)));
+            acc = fr_add(acc, fr_mul(tab_ld(m.beta[k], b), tab_ld(m.x[k], b)));
         acc = block_sum(acc, red);
         if (threadIdx.x == 0) part[(size_t)k * gridDim.x + blockIdx.x] = acc;
         __syncthreads();
@@ -123,14 +124,17 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_mg_weights(const DevState* st, MgT
 
 int zk_merge(zkdl_ctx* ctx, int K, const FrTab* beta, FrTab x, FrTab p, int d, void* work_mem) {
     MgTabs m;
-    for (int k = 0; k < ZKDL_REINDEX_MAX_K; ++k) m.beta[k] = k < K ? beta[k] : make_tab(nullptr, 0);
+    for (int k = 0; k < ZKDL_REINDEX_MAX_K; ++k) {
+        m.beta[k] = k < K ? beta[k] : make_tab(nullptr, 0);
+        m.x[k] = k < K ? x : make_tab(nullptr, 0);
+    }
     const uint64_t n = (uint64_t)1 << d;
     const int claims_scal = 8;
     uint64_t blocks = (n + ZK_BLOCK - 1) / ZK_BLOCK;
     const unsigned nblk = (unsigned)(blocks < (uint64_t)ZK_MAX_PART_BLOCKS ? blocks : (uint64_t)ZK_MAX_PART_BLOCKS);
     zk_flush_frames(ctx);
     // ctx->partials holds ZK_MAX_PART_BLOCKS * ZK_MAX_EVALS * 2 elements >= K * nblk for K <= 8
-    hipLaunchKernelGGL(k_mg_claims_part, dim3(nblk), dim3(ZK_BLOCK), 0, ctx->stream, m, K, x, n, ctx->partials);
+    hipLaunchKernelGGL(k_mg_claims_part, dim3(nblk), dim3(ZK_BLOCK), 0, ctx->stream, m, K, n, ctx->partials);
     hipLaunchKernelGGL(k_mg_claims_sum, dim3(K), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev,
                        (const Fr*)ctx->partials, (int)nblk, claims_scal);
     const int chal_base = ctx->n_chal;
@@ -142,4 +146,114 @@ int zk_merge(zkdl_ctx* ctx, int K, const FrTab* beta, FrTab x, FrTab p, int d, v
     hipLaunchKernelGGL(k_mg_weights, dim3(wblk), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, m, K, chal_base, n, p);
     FrTab src[2] = {p, x};
     return zk_sumcheck_product(ctx, 2, src, work_mem, d, 0);
+}
+
+// ---------------------------------------------------------------------------
+// The same statement for a stack X [N, D] on tables of D (not N D) entries.  Claims X~(s_k, q_k):
+//  1. T[k, x] = X~(s_k, x) (the stack axis bound), E[k, x] = r_k beta~(q_k, x);
+//     sum_k r_k X~(s_k, q_k) = sum_{k, x} E[k, x] T[k, x]: product sumcheck over (k, x), k leading,
+//     challenges (rho, v); it leaves T~(rho, v) = sum_k beta~(rho, k) X~(s_k, v);
+//  2. Eq. sc-reindex with the common inner point v: T~(rho, v) = sum_i Pn[i] X~(i, v),
+//     Pn[i] = sum_k beta~(rho, k) beta~(s_k, i): product sumcheck over i, leaves X~(v_n, v).
+// ---------------------------------------------------------------------------
+// E[k, x] *= r_k for k < K (r_k = chal[chal_base + k]); rows K .. K2 - 1 of E and T are cleared
+__global__ __launch_bounds__(ZK_BLOCK) void k_ms_scale(const DevState* st, int chal_base, int K, int K2, uint64_t D,
+                                                       FrTab e, FrTab t) {
+    const uint64_t total = (uint64_t)K2 * D;
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < total; b += (uint64_t)gridDim.x * blockDim.x) {
+        const int k = (int)(b / D);
+        if (k < K) {
+            tab_st(e, b, fr_mul(st->chal[chal_base + k], tab_ld(e, b)));
+        } else {
+            tab_st(e, b, fr_zero());
+            tab_st(t, b, fr_zero());
+        }
+    }
+}
+
+// Pn[i] = sum_k brho[k] bs_k[i]
+__global__ __launch_bounds__(ZK_BLOCK) void k_ms_stack_weights(MgTabs bs, FrTab brho, int K, uint64_t N, FrTab pn) {
+    const uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    Fr acc = fr_mul(tab_ld(brho, 0), tab_ld(bs.beta[0], i));
+    for (int k = 1; k < K; ++k) acc = fr_add(acc, fr_mul(tab_ld(brho, k), tab_ld(bs.beta[k], i)));
+    tab_st(pn, i, acc);
+}
+
+int zk_stack_merge(zkdl_ctx* ctx, const StackMergeJob& job, std::vector<void*>& keep) {
+    const int K = job.K;
+    const uint64_t N = job.N, rows = job.rows, cols = job.cols, D = rows * cols;
+    int ln = 0, lr = 0, lc = 0, lk = 0;
+    while (((uint64_t)1 << ln) < N) ++ln;
+    while (((uint64_t)1 << lr) < rows) ++lr;
+    while (((uint64_t)1 << lc) < cols) ++lc;
+    while ((1 << lk) < K) ++lk;
+    const int ld = lr + lc, K2 = 1 << lk;
+    if (ctx->n_chal + K + lk + ld + ln > ZK_MAX_CHAL) return ZKDL_EINVAL;
+    size_t work = zk_sumcheck_work_bytes(2, lk + ld);
+    if (zk_sumcheck_work_bytes(2, ln) > work) work = zk_sumcheck_work_bytes(2, ln);
+    const uint64_t fr_elems = (uint64_t)K * N + K2 + rows + cols + 2 * (uint64_t)K2 * D + N * rows + 2 * N;
+    void* mem = zk_alloc(ctx, fr_elems * 32 + work);
+    if (!mem) return ZKDL_ENOMEM;
+    keep.push_back(mem);
+    uint32_t* w = (uint32_t*)mem;
+    auto take = [&](uint64_t n) {
+        FrTab t = make_tab(w, n);
+        w += 8 * n;
+        return t;
+    };
+    MgTabs bs, cl;
+    for (int k = 0; k < ZKDL_REINDEX_MAX_K; ++k) bs.beta[k] = bs.x[k] = cl.beta[k] = cl.x[k] = make_tab(nullptr, 0);
+    for (int k = 0; k < K; ++k) bs.beta[k] = take(N);
+    const FrTab brho = take(K2), br = take(rows), bc = take(cols);
+    const FrTab E = take((uint64_t)K2 * D), T = take((uint64_t)K2 * D);
+    const FrTab by_row = take(N * rows), Tn = take(N), Pn = take(N);
+    void* work_mem = w;
+
+    // beta~(s_k, .), beta~(q_k, .) into row k of E; T[k, .] = X~(s_k, .)
+    BetaJob jobs[2 * ZKDL_REINDEX_MAX_K];
+    for (int k = 0; k < K; ++k) {
+        jobs[2 * k] = BetaJob{job.point[k], ln, bs.beta[k]};
+        jobs[2 * k + 1] = BetaJob{job.point[k] + ln, ld, tab_offset(E, (uint64_t)k * D)};
+    }
+    int rc = zk_build_beta_many(ctx, jobs, 2 * K);
+    for (int k = 0; k < K && rc == ZKDL_OK; ++k)
+        rc = zk_partial_eval(ctx, job.kind, job.X, 1, N, D, bs.beta[k], tab_offset(T, (uint64_t)k * D));
+    if (rc != ZKDL_OK) return rc;
+    // the K claims sum_x beta~(q_k, x) T[k, x]
+    for (int k = 0; k < K; ++k) {
+        cl.beta[k] = tab_offset(E, (uint64_t)k * D);
+        cl.x[k] = tab_offset(T, (uint64_t)k * D);
+    }
+    const int claims_scal = 8;
+    const uint64_t blocks = (D + ZK_BLOCK - 1) / ZK_BLOCK;
+    const unsigned nblk = (unsigned)(blocks < (uint64_t)ZK_MAX_PART_BLOCKS ? blocks : (uint64_t)ZK_MAX_PART_BLOCKS);
+    zk_flush_frames(ctx);
+    hipLaunchKernelGGL(k_mg_claims_part, dim3(nblk), dim3(ZK_BLOCK), 0, ctx->stream, cl, K, D, ctx->partials);
+    hipLaunchKernelGGL(k_mg_claims_sum, dim3(K), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev,
+                       (const Fr*)ctx->partials, (int)nblk, claims_scal);
+    const int chal_base = ctx->n_chal;
+    hipLaunchKernelGGL(k_ri_absorb, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, claims_scal, K,
+                       (uint32_t)ctx->proof_len, chal_base);
+    ctx->proof_len += 32 * (size_t)K;
+    ctx->n_chal += K;
+    const uint64_t sblocks = ((uint64_t)K2 * D + ZK_BLOCK - 1) / ZK_BLOCK;
+    hipLaunchKernelGGL(k_ms_scale, dim3((unsigned)(sblocks < 4096 ? sblocks : 4096)), dim3(ZK_BLOCK), 0, ctx->stream,
+                       ctx->dev, chal_base, K, K2, D, E, T);
+    const int c1 = ctx->n_chal;   // rho (lk), then v (rows first, then columns)
+    FrTab src[2] = {E, T};
+    rc = zk_sumcheck_product(ctx, 2, src, work_mem, lk + ld, 0);
+    if (rc != ZKDL_OK) return rc;
+
+    const Fr* chal = ctx->dev->chal;
+    const BetaJob j2[3] = {{chal + c1, lk, brho}, {chal + c1 + lk, lr, br}, {chal + c1 + lk + lr, lc, bc}};
+    rc = zk_build_beta_many(ctx, j2, 3);
+    // X~(i, v): the columns first, then the rows
+    if (rc == ZKDL_OK) rc = zk_partial_eval(ctx, job.kind, job.X, N * rows, cols, 1, bc, by_row);
+    if (rc == ZKDL_OK) rc = zk_partial_eval(ctx, TK_FR, &by_row, N, rows, 1, br, Tn);
+    if (rc != ZKDL_OK) return rc;
+    hipLaunchKernelGGL(k_ms_stack_weights, dim3((unsigned)((N + ZK_BLOCK - 1) / ZK_BLOCK)), dim3(ZK_BLOCK), 0,
+                       ctx->stream, bs, brho, K, N, Pn);
+    FrTab src2[2] = {Pn, Tn};
+    return zk_sumcheck_product(ctx, 2, src2, work_mem, ln, 0);
 }

@@ -173,6 +173,20 @@ int zk_reindex(zkdl_ctx* ctx, const ReindexJob& job, FrTab t, FrTab p, int ln, v
 // finals at scal[0], scal[1]
 int zk_merge(zkdl_ctx* ctx, int K, const FrTab* beta, FrTab x, FrTab p, int d, void* work_mem);
 
+// The same for a stack X [N, rows * cols] on tables of the inner size: claim k at the ln + ld
+// challenges from point[k] on (stack coordinates first).  Claims -> scal[8 ..) and the proof; K
+// coefficients drawn; two product sumchecks (inner over (k, x), then over the stack index), the last
+// finals at scal[0], scal[1].  The work memory is appended to `keep` (free it once the stream has
+// drained).
+struct StackMergeJob {
+    int K;
+    const Fr* point[ZKDL_REINDEX_MAX_K];   // device, Montgomery form
+    int kind;                              // TK_*
+    const void* X;                         // TK_FR: const FrTab*; else the integers (device)
+    uint64_t N, rows, cols;
+};
+int zk_stack_merge(zkdl_ctx* ctx, const StackMergeJob& job, std::vector<void*>& keep);
+
 // ---- k_zkrelu.hip ----------------------------------------------------------------
 // optimized aggregated matrix-product protocol: stack rounds with f_t, then the single-product sumcheck
 int zk_matmul_ft(zkdl_ctx* ctx, const FrTab* src, void* work_mem, int ln, int l2, const FrTab* wsuf, int w_idx,

@@ -131,13 +131,26 @@ def merge_case():
             "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
 
 
+def stack_merge_case():
+    """Two claims on a stack of 4 tensors of 8 elements merged on tables of the inner size (Eq. sc-reindex)."""
+    rng = np.random.default_rng(20230721)
+    x = rng.integers(-50, 50, (4, 8)).astype(np.int64)
+    pts = [uniform_fr_limbs(rng, 5).tobytes() for _ in range(2)]
+    ts = Transcript(15)
+    buf, info = P.stack_merge_prove(fr_array(x), 4, 8, [list(fr_array_from_le(p, 5)) for p in pts], ts)
+    return {"protocol": "claims_merge_stack_prove", "cite": "Sec. 2.2, Eq. sc-reindex, Protocol zkdl", "seed": 15,
+            "x": x.reshape(-1).tolist(), "x_shape": [4, 8], "points_le_hex": [p.hex() for p in pts],
+            "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
+
+
 if __name__ == "__main__":
     for name, fn in (("product_k3_d3", product_case), ("matmul_n2_2x4x2", matmul_case),
                      ("matmul_ft_n2_2x4x2", matmul_ft_case),
                      ("zkrelu_d4_q5_r3", zkrelu_case), ("zkrelu_at_d4_q5_r3", zkrelu_at_case),
                      ("aggregate_l2_w4_b2_t2", aggregate_case),
                      ("aggregate_linked_l2_w4_b2_t2", aggregate_linked_case),
-                     ("reindex_n4_d8_k2", reindex_case), ("merge_d4_k3", merge_case)):
+                     ("reindex_n4_d8_k2", reindex_case), ("merge_d4_k3", merge_case),
+                     ("stack_merge_n4_d8_k2", stack_merge_case)):
         with open(os.path.join(HERE, name + ".json"), "w") as f:
             json.dump(fn(), f, indent=1)
             f.write("\n")

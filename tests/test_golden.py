@@ -40,6 +40,9 @@ def oracle_run(g):
     elif g["protocol"] == "claims_merge_prove":
         pts = [[int(v) for v in fr_array_from_le(bytes.fromhex(h), len(h) // 64)] for h in g["points_le_hex"]]
         buf = P.merge_prove(fr_array(np.array(g["x"])), pts, ts)[0]
+    elif g["protocol"] == "claims_merge_stack_prove":
+        pts = [[int(v) for v in fr_array_from_le(bytes.fromhex(h), len(h) // 64)] for h in g["points_le_hex"]]
+        buf = P.stack_merge_prove(fr_array(np.array(g["x"])), g["x_shape"][0], g["x_shape"][1], pts, ts)[0]
     elif g["protocol"] == "aggregate_prove_linked":
         buf = P.aggregate_linked_prove(fcnn_window(2307162730 + 90, 2, 4, 2, 2), ts)[0]
     else:
@@ -60,7 +63,7 @@ def _without_repeats(points, drawn):
 
 
 NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "zkrelu_d4_q5_r3", "zkrelu_at_d4_q5_r3", "aggregate_l2_w4_b2_t2",
-         "aggregate_linked_l2_w4_b2_t2", "merge_d4_k3",
+         "aggregate_linked_l2_w4_b2_t2", "merge_d4_k3", "stack_merge_n4_d8_k2",
          "reindex_n4_d8_k2"]
 
 
@@ -94,10 +97,11 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
         pts = [[int(v) for v in fr_array_from_le(bytes.fromhex(h), len(h) // 64)] for h in g["points_le_hex"]]
         u = [int(v) for v in fr_array_from_le(bytes.fromhex(g["u_le_hex"]), len(g["u_le_hex"]) // 64)]
         got = lib.reindex_prove(ctx, x, g["maps"], pts, u, tr)
-    elif g["protocol"] == "claims_merge_prove":
-        x = lib.fr_tensor_upload(ctx, np.array(g["x"], dtype=np.int64), (len(g["x"]),))
+    elif g["protocol"] in ("claims_merge_prove", "claims_merge_stack_prove"):
+        stack = g["protocol"] == "claims_merge_stack_prove"
+        x = lib.fr_tensor_upload(ctx, np.array(g["x"], dtype=np.int64), tuple(g["x_shape"]) if stack else (len(g["x"]),))
         pts = [[int(v) for v in fr_array_from_le(bytes.fromhex(h), len(h) // 64)] for h in g["points_le_hex"]]
-        got = lib.claims_merge_prove(ctx, x, pts, tr)
+        got = lib.claims_merge_prove(ctx, x, pts, tr, stack=stack)
     elif g["protocol"] == "zkrelu_prove":
         got = lib.zkrelu_prove(ctx, np.array(g["Z"], dtype=np.int64), np.array(g["GA"], dtype=np.int64), tr, g["Q"], g["R"])
     elif g["protocol"] == "zkrelu_prove_at":

@@ -287,6 +287,45 @@ def test_claims_merge(lib, ctx, shape, k, kind):
             assert c == _stack_mle(st, pt[:1], pt[1:11], pt[11:])
 
 
+@pytest.mark.parametrize("shape,k,kind", [((4, 8), 2, "fr"), ((1, 8), 2, "i32"), ((8, 1), 2, "i64"), ((2, 2), 5, "fr"),
+                                          ((4, 8, 16), 3, "i32"), ((16, 64, 32), 1, "i32"), ((2, 1, 2048), 2, "fr"),
+                                          ((8, 1024, 1024), 2, "i32")])
+def test_claims_merge_stack(lib, ctx, shape, k, kind):
+    """The merge on tables of the inner size: proof bytes, claims, challenges and transcript agree."""
+    import torch
+    n = int(np.prod(shape))
+    d = n.bit_length() - 1
+    say(f"claims_merge_stack shape={shape} K={k} {kind}")
+    rng = np.random.default_rng(n + 3 * k)
+    pts = [fr_array_from_le(rand_fr_bytes(90 + j, d), d).tolist() for j in range(k)]
+    if kind == "fr":
+        raw = rand_fr_bytes(n + 2, n)
+        x = lib.fr_tensor_upload(ctx, raw, shape)
+        xo = fr_array_from_le(raw, n)
+    else:
+        dt = np.int32 if kind == "i32" else np.int64
+        vals = rng.integers(-2 ** 31, 2 ** 31, n).astype(dt)
+        x = lib.tensor_wrap_int(ctx, torch.from_numpy(vals).cuda(), shape)
+        xo = None
+    tr = lib.Transcript(36)
+    got = lib.claims_merge_prove(ctx, x, pts, tr, stack=True)
+    ots = OracleTranscript(36)
+    if n <= 1 << 15:
+        if xo is None:
+            xo = fr_array(vals)
+        buf, info = P.stack_merge_prove(xo, shape[0], n // shape[0], pts, ots)
+        assert got["proof"] == buf
+        assert got["points"] == ots.challenges
+        assert got["claims"][:k] == info["claims"] and got["claims"][k + 1] == info["outer"].finals[1]
+        assert tr.digest() == ots.digest()
+    else:
+        claims, point, left = P.stack_merge_verify(got["proof"], shape[0], n // shape[0], pts, ots)
+        assert tr.digest() == ots.digest() and got["points"] == ots.challenges
+        st = vals.reshape(shape)
+        for c, pt in zip(claims + [left], pts + [point]):
+            assert c == _stack_mle(st, pt[:3], pt[3:13], pt[13:])
+
+
 def test_claims_merge_rejects_bad_arguments(lib, ctx):
     say("claims_merge bad arguments")
     x = lib.fr_tensor_upload(ctx, rand_fr_bytes(1, 8), (8,))

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from oracle.field import R_MOD, fr_array, to_le
-from oracle.mle import mle_eval, beta_table
+from oracle.mle import mle_eval, beta_table, ilog2
 from oracle.sumcheck import lagrange_eval, prove, SumcheckProof
 from oracle import protocols as P
 from oracle.transcript import Transcript
@@ -308,3 +308,60 @@ def test_merge_verifier_rejects_tampering_and_wrong_points():
         other[1][2] = (other[1][2] + 1) % R_MOD
         with pytest.raises(AssertionError):
             P.merge_verify(b2, d, other, Transcript(16), bind_statement=bind)
+
+
+@pytest.mark.parametrize("n,d,k", [(4, 8, 2), (2, 4, 3), (1, 8, 2), (8, 1, 2), (4, 4, 1), (2, 2, 5)])
+def test_stack_merge_against_definitions(n, d, k):
+    """The two-step merge on a stack: claims are MLE evaluations; the inner sumcheck's claim is
+    the plain double sum over (k, x); its final on T is the combination of evaluations at the
+    common inner point v that Eq. sc-reindex starts from; the claim left is X~(v_n, v)."""
+    rng = np.random.default_rng(500 + 100 * n + 10 * d + k)
+    flat = fr_array(rng.integers(-1000, 1000, (n, d)))
+    x = np.asarray(flat, dtype=object).reshape(n, d)
+    ln, ld = ilog2(n), ilog2(d)
+    pts = [[int.from_bytes(rng.bytes(40), "little") % R_MOD for _ in range(ln + ld)] for _ in range(k)]
+    ts = Transcript(17)
+    buf, info = P.stack_merge_prove(flat, n, d, pts, ts)
+    assert info["claims"] == [mle_eval(flat, pt) for pt in pts]
+    r, rho, v, vn = info["r"], info["rho"], info["v"], info["vn"]
+    # inner claim: sum_k r_k sum_x beta~(q_k, x) X~(s_k, x), every X~(s_k, x) from the definition
+    total = 0
+    for rk, pt in zip(r, pts):
+        bs, bq = beta_table(pt[:ln]), beta_table(pt[ln:])
+        for xx in range(d):
+            t = sum(int(bs[i]) * int(x[i, xx]) for i in range(n)) % R_MOD
+            total += rk * int(bq[xx]) * t
+    assert info["inner"].claim0 == total % R_MOD
+    b_rho = beta_table(rho)
+    assert info["inner"].finals[1] == sum(int(b_rho[j]) * mle_eval(flat, pt[:ln] + v)
+                                          for j, pt in enumerate(pts)) % R_MOD
+    assert info["outer"].claim0 == info["inner"].finals[1]
+    assert info["outer"].finals[1] == mle_eval(flat, vn + v)
+    tv = Transcript(17)
+    claims, point, left = P.stack_merge_verify(buf, n, d, pts, tv)
+    assert tv.digest() == ts.digest() and claims == info["claims"]
+    assert point == vn + v and left == mle_eval(flat, point)
+    buf2, _ = P.stack_merge_prove(flat, n, d, pts, Transcript(17), bind_statement=False)
+    P.stack_merge_verify(buf2, n, d, pts, Transcript(17), bind_statement=False)
+    assert buf2[:16] == buf[:16]
+
+
+def test_stack_merge_verifier_rejects_tampering_and_wrong_points():
+    rng = np.random.default_rng(78)
+    n, d = 4, 4
+    x = fr_array(rng.integers(-50, 50, n * d))
+    pts = [[int.from_bytes(rng.bytes(40), "little") % R_MOD for _ in range(4)] for _ in range(2)]
+    buf, _ = P.stack_merge_prove(x, n, d, pts, Transcript(18))
+    P.stack_merge_verify(buf, n, d, pts, Transcript(18))
+    for off in list(range(16, len(buf), 41)) + [len(buf) - 1]:
+        bad = bytearray(buf)
+        bad[off] ^= 1
+        with pytest.raises(AssertionError):
+            P.stack_merge_verify(bytes(bad), n, d, pts, Transcript(18))
+    for bind in (True, False):
+        b2, _ = P.stack_merge_prove(x, n, d, pts, Transcript(18), bind_statement=bind)
+        for which in (0, 3):       # a stack coordinate, an inner coordinate
+            other = [list(pts[0]), list(pts[1])]
+            other[1][which] = (other[1][which] + 1) % R_MOD
+            with pytest.raises(AssertionError):
+                P.stack_merge_verify(b2, n, d, other, Transcript(18), bind_statement=bind)
