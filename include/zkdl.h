@@ -238,8 +238,7 @@ int claims_merge_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const zkdl_fr
  * sc-reindex, T~(rho, v) = sum_i Pn[i] X~(i, v), Pn[i] = sum_k beta~(rho, k) beta~(s_k, i), a
  * product sumcheck over i, leaves X~(v_n, v).  The verifier computes E~(rho, v), Pn~(v_n) and
  * checks that the second sumcheck starts from the first one's final on T.
- * A 3-d (or higher) tensor is taken as [N, rows, cols...]: X~(i, v) is evaluated columns
- * first.  claims (host, K + 2, may be NULL): the K claims, Pn~(v_n), X~(v_n, v).
+ * claims (host, K + 2, may be NULL): the K claims, Pn~(v_n), X~(v_n, v).
  * Transcript: "merge_stack" with the SHA-256 digest of u32le N, D, K and the points' bytes;
  * "c" the K claims; one draw of K; the two product sumchecks, each with its claim_0.
  * Proof: "ZKMS", N, D, K, the K claims, two SC blocks.  Errors as claims_merge_prove. */

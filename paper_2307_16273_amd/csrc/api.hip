@@ -987,30 +987,40 @@ extern "C" int reindex_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const i
     if (rc == ZKDL_OK) rc = upload_bytes(ctx, row_off.data(), (N + 1) * 4, &d_row);
     if (rc == ZKDL_OK) rc = upload_bytes(ctx, ent.data(), total * 4, &d_ent);
     if (rc == ZKDL_OK) rc = upload_bytes(ctx, maps_flat.data(), total * 4, &d_maps);
-    // device memory: Montgomery points | beta_u [D] | beta_k [len k] | T [N] | P [N] | sumcheck work
-    const size_t fr_elems = (size_t)(npts > 0 ? npts : 1) + D + total + 2 * N;
+    // X~(i, u) is taken in two steps over the row-major inner index x = (x_hi, x_lo): the low half of
+    // u's coordinates first (N * hi dot products of length lo), then the high half
+    const int lhi = ld / 2;
+    const uint64_t hi = (uint64_t)1 << lhi, lo = D >> lhi;
+    // device memory: Montgomery points | beta_hi | beta_lo | by_hi [N hi] | beta_k [len k] | T [N] | P [N] | work
+    const size_t fr_elems = (size_t)(npts > 0 ? npts : 1) + hi + lo + N * hi + total + 2 * N;
     void* mem = rc == ZKDL_OK ? zk_alloc(ctx, fr_elems * 32 + zk_sumcheck_work_bytes(2, ln)) : nullptr;
     if (rc == ZKDL_OK && !mem) rc = ZKDL_ENOMEM;
     if (rc == ZKDL_OK) {
         Fr* pm = (Fr*)mem;
         uint32_t* w = (uint32_t*)mem + 8 * (size_t)(npts > 0 ? npts : 1);
         if (npts > 0) zk_launch_points_to_mont(ctx, (const uint8_t*)d_pts, npts, pm);
-        BetaJob jobs[ZKDL_REINDEX_MAX_K + 1];
+        BetaJob jobs[ZKDL_REINDEX_MAX_K + 2];
         ReindexJob job;
         job.K = K;
         jobs[0].point = pm;
-        jobs[0].m = ld;
-        jobs[0].out = make_tab(w, D);
-        w += 8 * D;
+        jobs[0].m = lhi;
+        jobs[0].out = make_tab(w, hi);
+        w += 8 * hi;
+        jobs[1].point = pm + lhi;
+        jobs[1].m = ld - lhi;
+        jobs[1].out = make_tab(w, lo);
+        w += 8 * lo;
+        const FrTab by_hi = make_tab(w, N * hi);
+        w += 8 * N * hi;
         const Fr* pk = pm + ld;
         const int32_t* mk = (const int32_t*)d_maps;
         for (int k = 0; k < K; ++k) {
-            jobs[1 + k].point = pk;
-            jobs[1 + k].m = lk[k];
-            jobs[1 + k].out = make_tab(w, map_len[k]);
+            jobs[2 + k].point = pk;
+            jobs[2 + k].m = lk[k];
+            jobs[2 + k].out = make_tab(w, map_len[k]);
             job.map[k] = mk;
             job.len[k] = map_len[k];
-            job.beta[k] = jobs[1 + k].out;
+            job.beta[k] = jobs[2 + k].out;
             w += 8 * map_len[k];
             pk += lk[k];
             mk += map_len[k];
@@ -1021,11 +1031,12 @@ extern "C" int reindex_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const i
         w += 8 * N;
         const FrTab P = make_tab(w, N);
         w += 8 * N;
-        rc = zk_build_beta_many(ctx, jobs, K + 1);
+        rc = zk_build_beta_many(ctx, jobs, K + 2);
         if (rc == ZKDL_OK) {
             FrTab xs = make_tab(X->data, X->numel);
             const void* sp = X->kind == TK_FR ? (const void*)&xs : X->data;
-            rc = zk_partial_eval(ctx, X->kind, sp, N, D, 1, jobs[0].out, T);
+            rc = zk_partial_eval(ctx, X->kind, sp, N * hi, lo, 1, jobs[1].out, by_hi);
+            if (rc == ZKDL_OK) rc = zk_partial_eval(ctx, TK_FR, &by_hi, N, hi, 1, jobs[0].out, T);
         }
         if (rc == ZKDL_OK) rc = zk_reindex(ctx, job, T, P, ln, w);
     }
@@ -1133,7 +1144,9 @@ extern "C" int claims_merge_stack_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int
                                         zkdl_fr* points_out, size_t* npoints) {
     if (!ctx || !X || !tr || K < 1 || K > ZKDL_REINDEX_MAX_K || X->ndim < 1 || !is_pow2(X->numel)) return ZKDL_EINVAL;
     const uint64_t N = X->shape[0], D = X->numel / N;
-    const uint64_t rows = X->ndim >= 3 ? X->shape[1] : 1, cols = D / rows;
+    // the row-major inner index as (rows, cols) with about equally many bits each: X~(i, v) is taken
+    // over the columns first
+    const uint64_t rows = (uint64_t)1 << (ilog2_u64(D) / 2), cols = D / rows;
     const int d = ilog2_u64(X->numel);
     if (d > 0 && !points) return ZKDL_EINVAL;
     if (N > ((uint64_t)1 << 29) || D > ((uint64_t)1 << 29)) return ZKDL_EINVAL;
