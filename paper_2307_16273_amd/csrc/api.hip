@@ -1330,30 +1330,23 @@ extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_t
 // ---------------------------------------------------------------------------
 static const uint32_t ZKAL_MAGIC = 0x4C414B5Au;
 
-// The index maps of a re-indexing inside a larger proof (K sub-stacks of N entries each), inverted
-// and copied to the device.  Uploaded before the proof's kernels are enqueued: the copies read
-// pageable memory and would otherwise wait for everything enqueued before them.
+// The index maps of the re-indexings of a chained window on the device: K = 2 (the stack itself and the
+// stack shifted by one layer) or K = 1 (the shifted stack alone).
 struct RiPrepared {
     int K = 0;
     void *d_row = nullptr, *d_ent = nullptr, *d_maps = nullptr;
-    std::vector<uint32_t> row_off, ent, maps_flat;   // live until the stream has drained
 };
 
-static int prepare_reindex_linked(zkdl_ctx* ctx, uint64_t N, int K, const std::vector<int32_t>* maps,
-                                  RiPrepared& out) {
-    const int32_t* mp[ZKDL_REINDEX_MAX_K];
-    uint64_t lens[ZKDL_REINDEX_MAX_K];
-    for (int k = 0; k < K; ++k) {
-        mp[k] = maps[k].data();
-        lens[k] = N;
-    }
-    out.K = K;
-    build_inverse_maps(K, mp, lens, N, out.row_off, out.ent, out.maps_flat);
-    const uint64_t total = (uint64_t)K * N;
-    int rc = upload_bytes(ctx, out.row_off.data(), (N + 1) * 4, &out.d_row);
-    if (rc == ZKDL_OK) rc = upload_bytes(ctx, out.ent.data(), total * 4, &out.d_ent);
-    if (rc == ZKDL_OK) rc = upload_bytes(ctx, out.maps_flat.data(), total * 4, &out.d_maps);
-    return rc;
+static int prepare_layer_maps(zkdl_ctx* ctx, uint64_t N, uint32_t L, int with_ident, RiPrepared& out) {
+    out.K = with_ident ? 2 : 1;
+    const uint64_t total = (uint64_t)out.K * N;
+    out.d_row = zk_alloc(ctx, (N + 1) * 4);
+    out.d_ent = zk_alloc(ctx, total * 4);
+    out.d_maps = zk_alloc(ctx, total * 4);
+    if (!out.d_row || !out.d_ent || !out.d_maps) return ZKDL_ENOMEM;
+    zk_launch_layer_maps(ctx, (uint32_t)N, L, with_ident, (int32_t*)out.d_maps, (uint32_t*)out.d_row,
+                         (uint32_t*)out.d_ent);
+    return ZKDL_OK;
 }
 
 static void free_reindex_linked(zkdl_ctx* ctx, RiPrepared& p) {
@@ -1436,15 +1429,8 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
     // the index maps of the three re-indexings: the stack itself, and the stack whose slot (t, l)
     // is slot (t, l+1), zero for the last layer
     RiPrepared maps_a, maps_down;
-    {
-        std::vector<int32_t> both[2] = {std::vector<int32_t>(N), std::vector<int32_t>(N)};
-        for (uint64_t j = 0; j < N; ++j) {
-            both[0][j] = (int32_t)j;
-            both[1][j] = (j % w->L != w->L - 1) ? (int32_t)(j + 1) : -1;
-        }
-        rc = prepare_reindex_linked(ctx, N, 2, both, maps_a);
-        if (rc == ZKDL_OK) rc = prepare_reindex_linked(ctx, N, 1, both + 1, maps_down);
-    }
+    rc = prepare_layer_maps(ctx, N, w->L, 1, maps_a);
+    if (rc == ZKDL_OK) rc = prepare_layer_maps(ctx, N, w->L, 0, maps_down);
     uint32_t hw[6] = {w->L, w->B, w->width, w->T, w->Q, w->R};
     zk_absorb_words(ctx, "aggregate_linked", hw, 6);
     uint32_t hdr[8] = {ZKAL_MAGIC, w->L, w->B, w->width, w->T, w->Q, w->R, 0};

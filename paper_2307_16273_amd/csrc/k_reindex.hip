@@ -53,6 +53,33 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_ri_weights(const DevState* st, RiM
     tab_st(p, i, acc);
 }
 
+// The index maps of a chained window, written on the device (no copy from the host in the middle of a
+// proof): sub-stack "down" has slot j -> j + 1, none (-1) for the last of every L slots; with
+// with_ident the stack itself comes first (k = 0) and "down" is k = 1.  maps: the maps one after the
+// other; row_off / ent: their inverse by stack index, as ReindexJob takes it.
+__global__ void k_ri_layer_maps(uint32_t N, uint32_t L, int with_ident, int32_t* maps, uint32_t* row_off,
+                                uint32_t* ent) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > N) return;
+    const uint32_t shifted_before = i - (i + L - 1) / L;   // stack indices below i that "down" reaches
+    uint32_t off = with_ident ? i + shifted_before : shifted_before;
+    row_off[i] = off;
+    if (i == N) return;
+    const uint32_t kd = with_ident ? 1u : 0u;
+    if (with_ident) {
+        maps[i] = (int32_t)i;
+        ent[off++] = i;
+    }
+    maps[(with_ident ? N : 0u) + i] = (i % L != L - 1) ? (int32_t)(i + 1) : -1;
+    if (i % L != 0) ent[off] = (kd << 29) | (i - 1);
+}
+
+void zk_launch_layer_maps(zkdl_ctx* ctx, uint32_t N, uint32_t L, int with_ident, int32_t* maps, uint32_t* row_off,
+                          uint32_t* ent) {
+    hipLaunchKernelGGL(k_ri_layer_maps, dim3((N + 1 + ZK_BLOCK - 1) / ZK_BLOCK), dim3(ZK_BLOCK), 0, ctx->stream, N, L,
+                       with_ident, maps, row_off, ent);
+}
+
 int zk_reindex(zkdl_ctx* ctx, const ReindexJob& job, FrTab t, FrTab p, int ln, void* work_mem) {
     RiMaps m;
     for (int k = 0; k < ZKDL_REINDEX_MAX_K; ++k) {

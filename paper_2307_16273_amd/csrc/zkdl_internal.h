@@ -167,6 +167,9 @@ struct ReindexJob {
 // claims of the sub-stacks -> scal[8 ..), absorbed and written to the proof; K coefficients drawn;
 // P built into p; product sumcheck on (p, t) over ln variables, finals at scal[0], scal[1]
 int zk_reindex(zkdl_ctx* ctx, const ReindexJob& job, FrTab t, FrTab p, int ln, void* work_mem);
+// maps of a chained window built on the device: maps [K N], row_off [N + 1], ent [K N], K = 1 + with_ident
+void zk_launch_layer_maps(zkdl_ctx* ctx, uint32_t N, uint32_t L, int with_ident, int32_t* maps, uint32_t* row_off,
+                          uint32_t* ent);
 
 // K claims X~(p_k) on the table x (2^d entries) -> one: the claims -> scal[8 ..), absorbed and written
 // to the proof; K coefficients drawn; P = sum_k r_k beta[k] built into p; product sumcheck on (p, x),
