@@ -5,7 +5,8 @@ over the product of three tables of 2^24 uniform Fr elements (24 rounds) plus
 the partial evaluation of a 4096 x 4096 uniform Fr matrix at a random row point.
 Inputs are resident in HBM before the timed region.  Prints one JSON line:
 `value` = Fr elements through the step per second; `config` names the workload and carries the
-median times of its two parts, of the one-layer proofs and of the aggregated proofs of the
+median times of its two parts, of a Hadamard sumcheck on int32 stacks of the same size, of the
+one-layer proofs and of the aggregated proofs of the
 8 x 1024^2 (batch 64; one step, also with the claims chained, and 16 steps) and 4 x 4096^2
 (batch 256) networks; `roofline` =
 algorithmic bytes of the fused round kernels over their launch time measured with HIP events on
@@ -183,6 +184,13 @@ def main():
     up_med, _ = timed(lambda: zk.fr_tensor_upload(ctx, raw, (n,)).free(), 3)
     out["config"]["upload_fr_host_elems_per_s"] = n / up_med
     del raw
+    # sumcheck_hadamard on two int32 stacks of 2^24 values (conversion, the table of beta~(p, .), 24 rounds)
+    h0 = torch.from_numpy(rng.integers(-2 ** 31, 2 ** 31, n, dtype=np.int64).astype(np.int32)).cuda()
+    h1 = torch.from_numpy(rng.integers(-2 ** 31, 2 ** 31, n, dtype=np.int64).astype(np.int32)).cuda()
+    ha, hb = zk.tensor_wrap_int(ctx, h0, (n,)), zk.tensor_wrap_int(ctx, h1, (n,))
+    hd_med, _ = timed(lambda: zk.sumcheck_hadamard(ctx, ha, hb, zk.Transcript(6)), 3)
+    out["config"]["hadamard_int32_2p24_ms"] = 1e3 * hd_med
+    del ha, hb, h0, h1
     if not args.no_aggregate:
         # config 1: one FC layer 16 x 256 x 256 and its ReLU (forward only); latency-dominated
         from workloads import fc_relu_layer

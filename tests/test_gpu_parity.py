@@ -368,6 +368,32 @@ def test_sumcheck_hadamard(lib, ctx, shape):
     assert tr.digest() == ots.digest()
 
 
+def test_sumcheck_hadamard_full_size_by_properties(lib, ctx):
+    """Hadamard product of two stacks of 2^24 int32 values (the size of the micro-benchmark's
+    tables): the oracle's verifier replays all 24 rounds and ends in the library's transcript
+    state; the three claims are evaluated directly from the integers."""
+    import torch
+    say("sumcheck_hadamard 16 x 1024 x 1024")
+    shape = (16, 1024, 1024)
+    rng = np.random.default_rng(2024)
+    x0 = rng.integers(-2 ** 31, 2 ** 31, shape, dtype=np.int64).astype(np.int32)
+    x1 = rng.integers(-2 ** 31, 2 ** 31, shape, dtype=np.int64).astype(np.int32)
+    a = lib.tensor_wrap_int(ctx, torch.from_numpy(x0).cuda(), shape)
+    b = lib.tensor_wrap_int(ctx, torch.from_numpy(x1).cuda(), shape)
+    tr = lib.Transcript(7)
+    got = lib.sumcheck_hadamard(ctx, a, b, tr)
+    ots = OracleTranscript(7)
+    proof, pts = P.hadamard_verify(got["proof"], 24, ots)
+    assert tr.digest() == ots.digest() and got["points"] == ots.challenges
+    p, v = pts["p"], pts["v"]
+    assert got["claims"] == [proof.claim0, proof.finals[1], proof.finals[2]]
+    assert proof.finals[1] == _stack_mle(x0, v[:4], v[4:14], v[14:])
+    assert proof.finals[2] == _stack_mle(x1, v[:4], v[4:14], v[14:])
+    prod = x0.astype(np.int64) * x1.astype(np.int64)            # |.| < 2^62
+    assert proof.claim0 == _stack_mle(prod, p[:4], p[4:14], p[14:])
+    ctx.trim()
+
+
 def test_chained_calls_share_one_transcript(lib, ctx):
     say("chained calls")
     n = 64
