@@ -844,6 +844,46 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
     ctx->n_chal = d;
     FrView v0, v1;
     v0.scratch = v1.scratch = nullptr;
+    if (d >= ZK_HD_MIN_LOG) {
+        // large: beta~(p, .) is never a folded table; the rounds take beta~(p_[t+1:], .) as weights
+        const int t_tail = d - 10;
+        uint64_t suf_elems = 0;
+        for (int t = 0; t < t_tail; ++t) suf_elems += (uint64_t)1 << (d - t - 1);
+        void* mem = zk_alloc(ctx, suf_elems * 32 + 2048 * 36 + zk_sumcheck_work_bytes(2, d));
+        if (!mem) rc = ZKDL_ENOMEM;
+        if (rc == ZKDL_OK) rc = as_fr(ctx, X0, &v0);
+        if (rc == ZKDL_OK) rc = as_fr(ctx, X1, &v1);
+        if (rc == ZKDL_OK) {
+            std::vector<FrTab> wsuf(t_tail);
+            uint32_t* w = (uint32_t*)mem;
+            for (int t = 0; t < t_tail; ++t) {
+                const uint64_t cnt = (uint64_t)1 << (d - t - 1);
+                wsuf[t] = make_tab(w, cnt);
+                w += 8 * cnt;
+            }
+            F9Tab eq_tail;
+            eq_tail.p = w;
+            eq_tail.ps = 2048;
+            w += 9 * 2048;
+            // the smallest table (10 variables) by doubling, every larger one from the one before
+            rc = zk_build_beta(ctx, ctx->dev->chal + t_tail, d - t_tail, wsuf[t_tail - 1]);
+            if (rc == ZKDL_OK) zk_hadamard_suffix_tables(ctx, wsuf.data(), t_tail - 1, d, 0);
+            FrTab xs[2] = {v0.tab, v1.tab};
+            if (rc == ZKDL_OK) rc = zk_hadamard_eq(ctx, xs, wsuf.data(), w, eq_tail, d, 0, 0);
+        }
+        zkdl_fr tmp[3];
+        int ids[3] = {0, 1, 2};
+        int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 3, tmp);
+        if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims && proof) {
+            memcpy(claims[0].le, proof + 16, 32);
+            claims[1] = tmp[1];
+            claims[2] = tmp[2];
+        }
+        zk_free(ctx, mem);
+        zk_free(ctx, v0.scratch);
+        zk_free(ctx, v1.scratch);
+        return rc != ZKDL_OK ? rc : rc2;
+    }
     void* mem = zk_alloc(ctx, n * 32 + zk_sumcheck_work_bytes(3, d));
     if (!mem) rc = ZKDL_ENOMEM;
     if (rc == ZKDL_OK) rc = as_fr(ctx, X0, &v0);

@@ -820,3 +820,205 @@ void zk_launch_draw(zkdl_ctx* ctx, int chal_base, int count) {
     hipLaunchKernelGGL(k_frames_draw, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, f, chal_base,
                        count > 0 ? count : 0);
 }
+
+// ---------------------------------------------------------------------------
+// Hadamard product (Eq. exm-hadamard-batched) without a table for beta~(p, .) in the large rounds.
+// With the variables before t bound at v,
+//   g_t(x) = c_t l_t(x) f_t(x),   c_t = prod_{s<t} l_s(v_s),   l_t(x) = (1 - p_t)(1 - x) + p_t x,
+//   f_t(x) = sum_b beta~(p_[t+1:], b) X0'(x, b) X1'(x, b)      (degree 2),
+// so the rounds of k_ft_round (weight beta~(p_[t+1:], .) per pair index, inner size 1) give f_t at
+// 0, 1, 2, the finaliser extends it to 3 and multiplies the scalar factors back: the prover's
+// messages g_t(0..3) and the whole proof are those of the product sumcheck on (beta~(p, .), X0, X1),
+// while two tables are folded instead of three.  The last rounds run in the single-block kernel on
+// three tables; its table of the equality factor, c beta~(p_[t:], .), is written out for it.
+// ---------------------------------------------------------------------------
+struct HdFinArgs {
+    const Fr* part;        // block b: f(0), f(1), f(2) at part[3 b + x]
+    int nblk;
+    DevState* st;
+    int chal_idx;          // where the round's challenge goes
+    int p_idx;             // challenge index of p_t
+    int c_slot;            // scal[c_slot] = c_{t-1} on entry (t > 0), c_t on exit
+    uint32_t proof_off;    // where g_t(0..3) go
+    int first;             // round 0: c_0 = 1; claim_0 = g(0) + g(1) is written and absorbed first
+    uint32_t claim_off;
+};
+
+__global__ __launch_bounds__(ZK_BLOCK) void k_hd_finalise(HdFinArgs a) {
+    __shared__ TsShared S;
+    __shared__ Fr g[ZK_MAX_EVALS + 1];
+    __shared__ Fr fs[4];
+    __shared__ Fr cl[4];
+    DevState* st = a.st;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    block_ts_load(S, st);
+    // wave 3 has no partial sums to add: meanwhile it brings the scalar factor up to date,
+    // c_t = c_{t-1} l_{t-1}(v_{t-1}), l(v) = (1 - p) + v (2 p - 1), and forms c_t l_t(x), x = 0..3:
+    // l(0) = 1 - p, l(1) = p, l(2) = 3 p - 1, l(3) = 5 p - 2
+    if (wave == 3 && lane < 4) {
+        const Fr one = fr_const(frc::ONE);
+        Fr c = one;
+        if (!a.first) {
+            const Fr pp = st->chal[a.p_idx - 1], vp = st->chal[a.chal_idx - 1];
+            const Fr lv = fr_add(fr_sub(one, pp), fr_mul_ni(vp, fr_sub(fr_add(pp, pp), one)));
+            c = fr_mul_ni(st->scal[a.c_slot], lv);
+        }
+        const Fr p = st->chal[a.p_idx];
+        const Fr p2 = fr_add(p, p);
+        Fr l;
+        if (lane == 0) l = fr_sub(one, p);
+        else if (lane == 1) l = p;
+        else if (lane == 2) l = fr_sub(fr_add(p2, p), one);
+        else l = fr_sub(fr_add(fr_add(p2, p2), p), fr_add(one, one));
+        cl[lane] = fr_mul_ni(c, l);
+        if (lane == 0) st->scal[a.c_slot] = c;
+    }
+    block_reduce_partials(a.part, a.nblk, 3, fs);
+    if (threadIdx.x < 4) {
+        // f(3) = f(0) - 3 f(1) + 3 f(2)
+        const int x = threadIdx.x;
+        Fr f = fs[x < 3 ? x : 0];
+        if (x == 3) {
+            const Fr d21 = fr_sub(fs[2], fs[1]);
+            f = fr_add(fs[0], fr_add(d21, fr_add(d21, d21)));
+        }
+        g[x] = fr_mul_ni(cl[x], f);
+    }
+    __syncthreads();
+    if (a.first) {
+        if (threadIdx.x == 0) {
+            g[ZK_MAX_EVALS] = fr_add(g[0], g[1]);
+            st->lag_npts = 0;
+        }
+        __syncthreads();
+        block_absorb_frs(S, 'c', &g[ZK_MAX_EVALS], 1, (uint32_t*)(st->proof + a.claim_off));
+    }
+    block_round_challenge(S, st, g, 4, a.proof_off, a.chal_idx);
+    if (wave == 1) {
+        if (lane < 4) st->lag[lane] = S.tmp[lane];
+        if (lane == 0) {
+            st->lag_npts = 4;
+            st->lag_chal = (uint32_t)a.chal_idx;
+        }
+    }
+    block_ts_store(S, st);
+}
+
+// One more leading variable for a table of beta~: dst[b] = (1 - p) src[b], dst[b + n] = p src[b], b < n
+__global__ __launch_bounds__(ZK_BLOCK) void k_hd_suffix_expand(FrTab src, FrTab dst, uint64_t n, const Fr* p) {
+    const Fr pv = *p;
+    for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < n; b += (uint64_t)gridDim.x * blockDim.x) {
+        const Fr s0 = tab_ld(src, b);
+        const Fr hi = fr_mul(pv, s0);
+        tab_st(dst, b + n, hi);
+        tab_st(dst, b, fr_sub(s0, hi));
+    }
+}
+
+// wsuf[t] = beta~(p_[t+1:], .) for t = t_last - 1 .. 0 from wsuf[t_last] (each has one variable more)
+void zk_hadamard_suffix_tables(zkdl_ctx* ctx, const FrTab* wsuf, int t_last, int d, int p_idx) {
+    for (int t = t_last - 1; t >= 0; --t) {
+        const uint64_t n = (uint64_t)1 << (d - t - 2);   // entries of wsuf[t + 1]
+        const uint64_t want = (n + ZK_BLOCK - 1) / ZK_BLOCK;
+        hipLaunchKernelGGL(k_hd_suffix_expand, dim3((unsigned)(want < 8192 ? want : 8192)), dim3(ZK_BLOCK), 0, ctx->stream,
+                           wsuf[t + 1], wsuf[t], n, &ctx->dev->chal[p_idx + t + 1]);
+    }
+}
+
+// out[b] = scal[c_slot] * beta~((p_idx .. p_idx + nvars), b), b < 2^nvars, as a work table
+__global__ void k_hd_eq_tail(const DevState* st, int c_slot, int p_idx, int nvars, F9Tab out) {
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= (1u << nvars)) return;
+    const Fr one = fr_const(frc::ONE);
+    Fr acc = st->scal[c_slot];
+    for (int k = 0; k < nvars; ++k) {
+        const Fr pk = st->chal[p_idx + k];
+        acc = fr_mul_ni(acc, ((b >> (nvars - 1 - k)) & 1u) ? pk : fr_sub(one, pk));
+    }
+    f9tab_st(out, b, fr_unpack(acc));
+}
+
+// x: X0, X1 (packed, 2^d entries); wsuf[t], t < d - 10: beta~(p_[t+1:], .) with 2^(d-t-1) entries;
+// eq_tail: 2^11 work-table entries; p_idx: challenge index of p_0.  d >= ZK_HD_MIN_LOG.
+int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const FrTab* wsuf, void* work_mem, F9Tab eq_tail, int d, int p_idx,
+                   int finals_scal_base) {
+    constexpr int SC_TAIL_LOG = 10;
+    if (d < ZK_HD_MIN_LOG || ctx->n_chal + d > ZK_MAX_CHAL) return ZKDL_EINVAL;
+    zk_flush_frames(ctx);
+    uint32_t hdr[4] = {SC_MAGIC, 3, 3, (uint32_t)d};
+    zk_write_proof_words(ctx, hdr, 4);
+    const uint32_t claim_off = (uint32_t)ctx->proof_len;
+    const uint32_t rounds_off = claim_off + 32;
+    const uint32_t finals_off = rounds_off + (uint32_t)d * 128;
+    if (finals_off + 96 > (uint32_t)ZK_PROOF_CAP) return ZKDL_ESMALL;
+    ctx->proof_len = finals_off + 96;
+    const uint64_t half = (uint64_t)1 << (d - 1);
+    F9Tab work[2];
+    for (int k = 0; k < 2; ++k) {
+        work[k].p = (uint32_t*)work_mem + (size_t)k * half * 9;
+        work[k].ps = half;
+    }
+    const int first_chal = ctx->n_chal;
+    const int t_tail = d - SC_TAIL_LOG;
+    const int c_slot = 32;   // the scalar factor c_t of the last round closed
+    for (int t = 0; t < t_tail; ++t) {
+        const int mode = t == 0 ? 0 : t == 1 ? 1 : 2;
+        const uint64_t m = (uint64_t)1 << (d - t - 1);
+        const uint64_t want = (m + ZK_BLOCK - 1) / ZK_BLOCK;
+        const unsigned grid = (unsigned)(want > ZK_MAX_PART_BLOCKS ? ZK_MAX_PART_BLOCKS : want);
+        FtRoundArgs fa;
+        for (int k = 0; k < 2; ++k) {
+            fa.src8[k] = x[k];
+            fa.work[k] = work[k];
+        }
+        fa.m = m;
+        fa.log_inner = 0;
+        fa.wsuf = wsuf[t];
+        fa.chal = mode ? &ctx->dev->chal[first_chal + t - 1] : nullptr;
+        fa.part = ctx->partials;
+        // algorithmic bytes: two tables as in the product rounds, plus one weight per pair index
+        zk_prof_begin(ctx, mode ? ZKDL_PROF_SC_ROUND_FUSED : ZKDL_PROF_SC_ROUND_FIRST,
+                      (2.0 * (mode ? 192.0 : 64.0) + 32.0) * (double)m);
+        if (mode == 0) hipLaunchKernelGGL(k_ft_round<0>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+        else if (mode == 1) hipLaunchKernelGGL(k_ft_round<1>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+        else hipLaunchKernelGGL(k_ft_round<2>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+        zk_prof_end(ctx);
+        HdFinArgs hf;
+        hf.part = ctx->partials;
+        hf.nblk = (int)grid;
+        hf.st = ctx->dev;
+        hf.chal_idx = ctx->n_chal++;
+        hf.p_idx = p_idx + t;
+        hf.c_slot = c_slot;
+        hf.proof_off = rounds_off + (uint32_t)t * 128;
+        hf.first = t == 0;
+        hf.claim_off = claim_off;
+        zk_prof_begin(ctx, ZKDL_PROF_FINALISE, 128.0);
+        hipLaunchKernelGGL(k_hd_finalise, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, hf);
+        zk_prof_end(ctx);
+    }
+    // the single-block kernel folds its tables with the last challenge drawn above before its first
+    // round: the equality factor's table stands one challenge back, c_{t_tail - 1} beta~(p_[t_tail-1:], .)
+    const int nv = SC_TAIL_LOG + 1;
+    hipLaunchKernelGGL(k_hd_eq_tail, dim3((1u << nv) / ZK_BLOCK), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, c_slot,
+                       p_idx + t_tail - 1, nv, eq_tail);
+    ScTailArgs ta;
+    ta.ra.src8[0] = x[0];
+    ta.ra.work[0] = eq_tail;
+    for (int k = 0; k < 2; ++k) {
+        ta.ra.src8[1 + k] = x[k];
+        ta.ra.work[1 + k] = work[k];
+    }
+    ta.ra.m = (uint64_t)1 << (d - t_tail - 1);
+    ta.ra.chal = nullptr;
+    ta.ra.part = nullptr;
+    ta.rounds = d - t_tail;
+    ta.first_chal = first_chal + t_tail - 1;
+    ta.st = ctx->dev;
+    ta.rounds_off = rounds_off + (uint32_t)t_tail * 128;
+    ta.finals_off = finals_off;
+    ta.scal_base = finals_scal_base;
+    ctx->n_chal += d - t_tail;
+    launch_tail<3>(ctx, ta);
+    return ZKDL_OK;
+}

@@ -148,6 +148,15 @@ void zk_launch_shift_rows(zkdl_ctx* ctx, FrTab src, uint64_t rows, uint64_t inne
 size_t zk_sumcheck_work_bytes(int K, int d);
 int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, void* work_mem, int d,
                         int finals_scal_base);
+// The product sumcheck on (beta~(p, .), X0, X1) for 2^d entries, d >= ZK_HD_MIN_LOG, with two folded
+// tables: the same proof bytes and transcript as zk_sumcheck_product on the three tables.  x: X0, X1
+// packed; wsuf[t], t < d - 10: beta~(p_[t+1:], .), 2^(d-t-1) entries; eq_tail: 2^11 work-table
+// entries of scratch; work_mem: zk_sumcheck_work_bytes(2, d); p_idx: challenge index of p_0.
+constexpr int ZK_HD_MIN_LOG = 14;
+// wsuf[t_last] built; fills wsuf[t_last - 1] .. wsuf[0], each from the one after it
+void zk_hadamard_suffix_tables(zkdl_ctx* ctx, const FrTab* wsuf, int t_last, int d, int p_idx);
+int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const FrTab* wsuf, void* work_mem, F9Tab eq_tail, int d, int p_idx,
+                   int finals_scal_base);
 // Queues the frame of a protocol header (label, n <= 8 little-endian u32 words); it is absorbed
 // by the next zk_launch_draw / zk_flush_frames, in stream order before everything that follows.
 void zk_absorb_words(zkdl_ctx* ctx, const char* label, const uint32_t* words, int n);

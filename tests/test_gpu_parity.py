@@ -351,7 +351,7 @@ def test_reindex_prove_rejects_bad_arguments(lib, ctx):
     assert tr.digest() == before
 
 
-@pytest.mark.parametrize("shape", [(1,), (2, 4, 4), (4, 64, 16)])
+@pytest.mark.parametrize("shape", [(1,), (2, 4, 4), (4, 64, 16), (2, 64, 64), (16384,), (8, 64, 64), (32, 64, 64)])
 def test_sumcheck_hadamard(lib, ctx, shape):
     say(f"sumcheck_hadamard shape={shape}")
     rng = np.random.default_rng(17)
