@@ -851,8 +851,10 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
         for (int t = 0; t < t_tail; ++t) suf_elems += (uint64_t)1 << (d - t - 1);
         void* mem = zk_alloc(ctx, suf_elems * 32 + 2048 * 36 + zk_sumcheck_work_bytes(2, d));
         if (!mem) rc = ZKDL_ENOMEM;
-        if (rc == ZKDL_OK) rc = as_fr(ctx, X0, &v0);
-        if (rc == ZKDL_OK) rc = as_fr(ctx, X1, &v1);
+        // two int32 stacks are read as they are by the first two rounds: no conversion pass
+        const bool ints = X0->kind == TK_I32 && X1->kind == TK_I32;
+        if (rc == ZKDL_OK && !ints) rc = as_fr(ctx, X0, &v0);
+        if (rc == ZKDL_OK && !ints) rc = as_fr(ctx, X1, &v1);
         if (rc == ZKDL_OK) {
             std::vector<FrTab> wsuf(t_tail);
             uint32_t* w = (uint32_t*)mem;
@@ -869,7 +871,8 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
             rc = zk_build_beta(ctx, ctx->dev->chal + t_tail, d - t_tail, wsuf[t_tail - 1]);
             if (rc == ZKDL_OK) zk_hadamard_suffix_tables(ctx, wsuf.data(), t_tail - 1, d, 0);
             FrTab xs[2] = {v0.tab, v1.tab};
-            if (rc == ZKDL_OK) rc = zk_hadamard_eq(ctx, xs, wsuf.data(), w, eq_tail, d, 0, 0);
+            const int32_t* xi[2] = {(const int32_t*)X0->data, (const int32_t*)X1->data};
+            if (rc == ZKDL_OK) rc = zk_hadamard_eq(ctx, xs, ints ? xi : nullptr, wsuf.data(), w, eq_tail, d, 0, 0);
         }
         zkdl_fr tmp[3];
         int ids[3] = {0, 1, 2};

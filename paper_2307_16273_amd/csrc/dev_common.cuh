@@ -577,6 +577,73 @@ __device__ inline void block_reduce_partials(const Fr* part, int nblk, int npts,
     __syncthreads();
 }
 
+// ---- Montgomery form times plain integer --------------------------------------------------------
+// A value in Montgomery form times a plain integer is the Montgomery form of the product: such
+// products are accumulated as 64-bit columns of 29-bit limb products with no reduction, and reduced
+// once per thread or per output.
+// cols += c * mag for a normal or negated-normal c (limbs below 2^30.6) and mag < 2^58
+__device__ __forceinline__ void cols11_mac(uint64_t* cols, const F9& c, uint64_t mag) {
+    const uint32_t m0 = (uint32_t)mag & frc::M29, m1 = (uint32_t)(mag >> 29);
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+        cols[i] += (uint64_t)c.v[i] * m0;
+        cols[i + 1] += (uint64_t)c.v[i] * m1;
+    }
+}
+
+// cols += p * c for a signed c, |c| < 2^58, and a normal p below 2.6 r: a negative c turns p
+// into 4r - p
+__device__ __forceinline__ void cols11_mac_signed(uint64_t* cols, const F9& p, int64_t c) {
+    const bool neg = c < 0;
+    const uint64_t mag = neg ? (uint64_t)0 - (uint64_t)c : (uint64_t)c;
+    F9 q;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) q.v[i] = neg ? frc::C4R[i] - p.v[i] : p.v[i];
+    cols11_mac(cols, q, mag);
+}
+
+// carries of an 11-column accumulator: columns 0..9 below 2^29 afterwards
+__device__ __forceinline__ void cols11_carry(uint64_t* cols) {
+#pragma unroll
+    for (int k = 0; k + 1 < 11; ++k) {
+        cols[k + 1] += cols[k] >> 29;
+        cols[k] &= frc::M29;
+    }
+}
+
+// carried 11-column sum V -> lazy value congruent to it, normal and below 2.41 r:
+// V = low nine limbs + 2^261 * high part, and 2^261 is the Montgomery radix, so the high part
+// times R^2 as a Montgomery product is congruent to 2^261 * high part
+__device__ __forceinline__ F9 cols11_value(const uint64_t* cols) {
+    F9 vlo, vhi = f9_zero();
+#pragma unroll
+    for (int i = 0; i < 9; ++i) vlo.v[i] = (uint32_t)cols[i];
+    vhi.v[0] = (uint32_t)cols[9];
+    vhi.v[1] = (uint32_t)cols[10] & frc::M29;
+    vhi.v[2] = (uint32_t)(cols[10] >> 29) & frc::M29;
+    vhi.v[3] = (uint32_t)(cols[10] >> 58);
+    return f9_norm_reduce(f9_add(vlo, f9_mul(vhi, fr_unpack(fr_const(frc::R2)))));
+}
+
+// a0 + v0 (a2 - a0) in Montgomery form from the integers; k = (R^2, -R^2, v0 R^2, -v0 R^2),
+// canonical.  Four products below 2^58 per column; the result is normal and below 2 r.
+__device__ __forceinline__ F9 fold_ints(const F9* k, int64_t a0, int64_t a2) {
+    const int64_t d = a2 - a0;
+    const bool n0 = a0 < 0, nd = d < 0;
+    uint64_t cols[17];
+#pragma unroll
+    for (int c = 0; c < 17; ++c) cols[c] = 0;
+    F9 c0, cd;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+        c0.v[i] = n0 ? k[1].v[i] : k[0].v[i];
+        cd.v[i] = nd ? k[3].v[i] : k[2].v[i];
+    }
+    cols11_mac(cols, c0, n0 ? (uint64_t)0 - (uint64_t)a0 : (uint64_t)a0);
+    cols11_mac(cols, cd, nd ? (uint64_t)0 - (uint64_t)d : (uint64_t)d);
+    return f9_redc(cols);
+}
+
 // ---- launchers defined in k_sumcheck.hip ----
 void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_t proof_off, int first,
                         uint32_t claim_off, int derive1);

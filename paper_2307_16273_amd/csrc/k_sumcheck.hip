@@ -938,10 +938,115 @@ __global__ void k_hd_eq_tail(const DevState* st, int c_slot, int p_idx, int nvar
     f9tab_st(out, b, fr_unpack(acc));
 }
 
+// The first two rounds on int32 sources (no conversion pass).  Round 0: the lines of X0 and X1
+// through x = 0, 1, 2 are integers below 2^34 in magnitude, their products below 2^68, and a weight
+// in Montgomery form times such an integer is the Montgomery form of the product: 27 limb products
+// into 12 columns, no reduction until the thread's sum is complete.  Round 1 binds v_0 on the way,
+// a + v_0 (a' - a) = redc(R^2 |a| +- v_0 R^2 |a' - a|), and writes the folded work tables.
+struct HdIntArgs {
+    const int32_t* x[2];
+    F9Tab work[2];
+    uint64_t m;        // pair indices this round
+    FrTab wsuf;        // beta~(p_[t+1:], .), m entries
+    const Fr* chal;    // MODE 1: v_0
+    Fr* part;          // block b: f(0), f(1), f(2) at part[3 b + x]
+};
+
+// cols += w * (a * c) for a normal w below 2.6 r and |a|, |c| < 2^34; a negative product turns w into 4r - w
+__device__ __forceinline__ void cols12_mac_prod(uint64_t* cols, const F9& w, int64_t a, int64_t c) {
+    const bool neg = (a < 0) != (c < 0);
+    const uint64_t ua = a < 0 ? (uint64_t)0 - (uint64_t)a : (uint64_t)a;
+    const uint64_t uc = c < 0 ? (uint64_t)0 - (uint64_t)c : (uint64_t)c;
+    const uint64_t lo = ua * uc, hi = __umul64hi(ua, uc);   // the product is below 2^68
+    const uint32_t m0 = (uint32_t)lo & frc::M29, m1 = (uint32_t)(lo >> 29) & frc::M29;
+    const uint32_t m2 = (uint32_t)(lo >> 58) | ((uint32_t)hi << 6);
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+        const uint32_t wi = neg ? frc::C4R[i] - w.v[i] : w.v[i];
+        cols[i] += (uint64_t)wi * m0;
+        cols[i + 1] += (uint64_t)wi * m1;
+        cols[i + 2] += (uint64_t)wi * m2;
+    }
+#pragma unroll
+    for (int k = 0; k + 1 < 12; ++k) {   // columns 0..10 below 2^29 again
+        cols[k + 1] += cols[k] >> 29;
+        cols[k] &= frc::M29;
+    }
+}
+
+// carried 12-column sum -> lazy value congruent to it, normal and below 2.41 r (as cols11_value)
+__device__ __forceinline__ F9 cols12_value(const uint64_t* cols) {
+    F9 vlo, vhi = f9_zero();
+#pragma unroll
+    for (int i = 0; i < 9; ++i) vlo.v[i] = (uint32_t)cols[i];
+    vhi.v[0] = (uint32_t)cols[9];
+    vhi.v[1] = (uint32_t)cols[10];
+    vhi.v[2] = (uint32_t)cols[11] & frc::M29;
+    vhi.v[3] = (uint32_t)(cols[11] >> 29) & frc::M29;
+    vhi.v[4] = (uint32_t)(cols[11] >> 58);
+    return f9_norm_reduce(f9_add(vlo, f9_mul(vhi, fr_unpack(fr_const(frc::R2)))));
+}
+
+template <int MODE>
+__global__ __launch_bounds__(ZK_BLOCK) void k_hd_round_i32(HdIntArgs a) {
+    __shared__ uint32_t red[BLOCK_SUM_LAZY_WORDS];
+    __shared__ F9 kf[4];     // R^2, -R^2, v0 R^2, -v0 R^2
+    const uint64_t m = a.m;
+    F9 acc[3];
+    if (MODE == 0) {
+        uint64_t cols[3][12];
+#pragma unroll
+        for (int x = 0; x < 3; ++x)
+#pragma unroll
+            for (int c = 0; c < 12; ++c) cols[x][c] = 0;
+        for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+            const int64_t a0 = a.x[0][b], a1 = a.x[0][b + m], c0 = a.x[1][b], c1 = a.x[1][b + m];
+            const F9 w = fr_unpack(tab_ld(a.wsuf, b));
+            cols12_mac_prod(cols[0], w, a0, c0);
+            cols12_mac_prod(cols[1], w, a1, c1);
+            cols12_mac_prod(cols[2], w, 2 * a1 - a0, 2 * c1 - c0);
+        }
+#pragma unroll
+        for (int x = 0; x < 3; ++x) acc[x] = cols12_value(cols[x]);
+    } else {
+        if (threadIdx.x < 4) {
+            const Fr v0 = *a.chal, r2 = fr_const(frc::R2);
+            const Fr c = threadIdx.x < 2 ? r2 : fr_mul(v0, r2);
+            kf[threadIdx.x] = fr_unpack((threadIdx.x & 1) ? fr_neg(c) : c);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
+        for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+            F9 lo[2], hi[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int64_t t0 = a.x[k][b], t1 = a.x[k][b + m], t2 = a.x[k][b + 2 * m], t3 = a.x[k][b + 3 * m];
+                lo[k] = fold_ints(kf, t0, t2);
+                hi[k] = fold_ints(kf, t1, t3);
+                f9tab_st(a.work[k], b, lo[k]);
+                f9tab_st(a.work[k], b + m, hi[k]);
+            }
+            const F9 w = fr_unpack(tab_ld(a.wsuf, b));
+            const F9 wl = f9_mul(lo[0], w), wh = f9_mul(hi[0], w);
+            const F9 w2 = f9_norm(f9_add(wh, f9_norm(f9_sub(wh, wl))));
+            const F9 e2 = f9_add(hi[1], f9_norm(f9_sub(hi[1], lo[1])));
+            acc[0] = f9_add(acc[0], f9_mul(wl, lo[1]));
+            acc[1] = f9_add(acc[1], f9_mul(wh, hi[1]));
+            acc[2] = f9_add(acc[2], f9_mul(w2, e2));
+#pragma unroll
+            for (int x = 0; x < 3; ++x) acc[x] = f9_norm_reduce(acc[x]);
+        }
+    }
+    const Fr s = block_sum_lazy<3>(acc, red);
+    if (threadIdx.x < 3) a.part[(uint64_t)blockIdx.x * 3 + threadIdx.x] = s;
+}
+
 // x: X0, X1 (packed, 2^d entries); wsuf[t], t < d - 10: beta~(p_[t+1:], .) with 2^(d-t-1) entries;
 // eq_tail: 2^11 work-table entries; p_idx: challenge index of p_0.  d >= ZK_HD_MIN_LOG.
-int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const FrTab* wsuf, void* work_mem, F9Tab eq_tail, int d, int p_idx,
-                   int finals_scal_base) {
+// xi != nullptr: both sources are int32 arrays (device) and x is not read.
+int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const int32_t* const* xi, const FrTab* wsuf, void* work_mem,
+                   F9Tab eq_tail, int d, int p_idx, int finals_scal_base) {
     constexpr int SC_TAIL_LOG = 10;
     if (d < ZK_HD_MIN_LOG || ctx->n_chal + d > ZK_MAX_CHAL) return ZKDL_EINVAL;
     zk_flush_frames(ctx);
@@ -968,7 +1073,7 @@ int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const FrTab* wsuf, void* work_
         const unsigned grid = (unsigned)(want > ZK_MAX_PART_BLOCKS ? ZK_MAX_PART_BLOCKS : want);
         FtRoundArgs fa;
         for (int k = 0; k < 2; ++k) {
-            fa.src8[k] = x[k];
+            fa.src8[k] = xi ? make_tab(nullptr, 0) : x[k];
             fa.work[k] = work[k];
         }
         fa.m = m;
@@ -976,13 +1081,31 @@ int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const FrTab* wsuf, void* work_
         fa.wsuf = wsuf[t];
         fa.chal = mode ? &ctx->dev->chal[first_chal + t - 1] : nullptr;
         fa.part = ctx->partials;
-        // algorithmic bytes: two tables as in the product rounds, plus one weight per pair index
-        zk_prof_begin(ctx, mode ? ZKDL_PROF_SC_ROUND_FUSED : ZKDL_PROF_SC_ROUND_FIRST,
-                      (2.0 * (mode ? 192.0 : 64.0) + 32.0) * (double)m);
-        if (mode == 0) hipLaunchKernelGGL(k_ft_round<0>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
-        else if (mode == 1) hipLaunchKernelGGL(k_ft_round<1>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
-        else hipLaunchKernelGGL(k_ft_round<2>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
-        zk_prof_end(ctx);
+        if (xi && mode < 2) {
+            HdIntArgs ia;
+            for (int k = 0; k < 2; ++k) {
+                ia.x[k] = xi[k];
+                ia.work[k] = work[k];
+            }
+            ia.m = m;
+            ia.wsuf = wsuf[t];
+            ia.chal = fa.chal;
+            ia.part = ctx->partials;
+            // algorithmic bytes: the integers (2 or 4 per table), one weight, round 1 also the folded tables
+            zk_prof_begin(ctx, mode ? ZKDL_PROF_SC_ROUND_FUSED : ZKDL_PROF_SC_ROUND_FIRST,
+                          (mode ? 2.0 * (16.0 + 64.0) + 32.0 : 2.0 * 8.0 + 32.0) * (double)m);
+            if (mode == 0) hipLaunchKernelGGL(k_hd_round_i32<0>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, ia);
+            else hipLaunchKernelGGL(k_hd_round_i32<1>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, ia);
+            zk_prof_end(ctx);
+        } else {
+            // algorithmic bytes: two tables as in the product rounds, plus one weight per pair index
+            zk_prof_begin(ctx, mode ? ZKDL_PROF_SC_ROUND_FUSED : ZKDL_PROF_SC_ROUND_FIRST,
+                          (2.0 * (mode ? 192.0 : 64.0) + 32.0) * (double)m);
+            if (mode == 0) hipLaunchKernelGGL(k_ft_round<0>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+            else if (mode == 1) hipLaunchKernelGGL(k_ft_round<1>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+            else hipLaunchKernelGGL(k_ft_round<2>, dim3(grid), dim3(ZK_BLOCK), 0, ctx->stream, fa);
+            zk_prof_end(ctx);
+        }
         HdFinArgs hf;
         hf.part = ctx->partials;
         hf.nblk = (int)grid;
@@ -1003,12 +1126,9 @@ int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const FrTab* wsuf, void* work_
     hipLaunchKernelGGL(k_hd_eq_tail, dim3((1u << nv) / ZK_BLOCK), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, c_slot,
                        p_idx + t_tail - 1, nv, eq_tail);
     ScTailArgs ta;
-    ta.ra.src8[0] = x[0];
     ta.ra.work[0] = eq_tail;
-    for (int k = 0; k < 2; ++k) {
-        ta.ra.src8[1 + k] = x[k];
-        ta.ra.work[1 + k] = work[k];
-    }
+    for (int k = 0; k < 2; ++k) ta.ra.work[1 + k] = work[k];
+    for (int k = 0; k < 3; ++k) ta.ra.src8[k] = make_tab(nullptr, 0);   // the tail reads the work tables only
     ta.ra.m = (uint64_t)1 << (d - t_tail - 1);
     ta.ra.chal = nullptr;
     ta.ra.part = nullptr;

@@ -364,27 +364,6 @@ __device__ __forceinline__ void lin_body(const LinArgs& a, const unsigned bx, co
 // redc(R^2 |a| +- v0 R^2 |a' - a|), one reduction and no full product; the folded tables are written
 // out for the later rounds, which work on field elements as before.
 
-// cols += c * mag for a normal or negated-normal c (limbs below 2^30.6) and mag < 2^58
-__device__ __forceinline__ void cols11_mac(uint64_t* cols, const F9& c, uint64_t mag) {
-    const uint32_t m0 = (uint32_t)mag & frc::M29, m1 = (uint32_t)(mag >> 29);
-#pragma unroll
-    for (int i = 0; i < 9; ++i) {
-        cols[i] += (uint64_t)c.v[i] * m0;
-        cols[i + 1] += (uint64_t)c.v[i] * m1;
-    }
-}
-
-// cols += p * c for a signed c, |c| < 2^58, and a normal p below 2.6 r: a negative c turns p
-// into 4r - p
-__device__ __forceinline__ void cols11_mac_signed(uint64_t* cols, const F9& p, int64_t c) {
-    const bool neg = c < 0;
-    const uint64_t mag = neg ? (uint64_t)0 - (uint64_t)c : (uint64_t)c;
-    F9 q;
-#pragma unroll
-    for (int i = 0; i < 9; ++i) q.v[i] = neg ? frc::C4R[i] - p.v[i] : p.v[i];
-    cols11_mac(cols, q, mag);
-}
-
 // lo + x (hi - lo) at x = 0, 2, 3, each normal and below 2.41 r
 __device__ __forceinline__ void line3_reduced(const F9& lo, const F9& hi, F9 e[3]) {
     const F9 dn = f9_norm(f9_sub(hi, lo));
@@ -402,29 +381,6 @@ __device__ __forceinline__ IntRow int_row(int64_t z, int nbits, int r_bits) {
     r.zp = rescale_half_up(z, r_bits);
     r.ns = 1 - ((z >> (nbits - 1)) & 1);
     return r;
-}
-
-// carries of an 11-column accumulator: columns 0..9 below 2^29 afterwards
-__device__ __forceinline__ void cols11_carry(uint64_t* cols) {
-#pragma unroll
-    for (int k = 0; k + 1 < 11; ++k) {
-        cols[k + 1] += cols[k] >> 29;
-        cols[k] &= frc::M29;
-    }
-}
-
-// carried 11-column sum V -> lazy value congruent to it, normal and below 2.41 r:
-// V = low nine limbs + 2^261 * high part, and 2^261 is the Montgomery radix, so the high part
-// times R^2 as a Montgomery product is congruent to 2^261 * high part
-__device__ __forceinline__ F9 cols11_value(const uint64_t* cols) {
-    F9 vlo, vhi = f9_zero();
-#pragma unroll
-    for (int i = 0; i < 9; ++i) vlo.v[i] = (uint32_t)cols[i];
-    vhi.v[0] = (uint32_t)cols[9];
-    vhi.v[1] = (uint32_t)cols[10] & frc::M29;
-    vhi.v[2] = (uint32_t)(cols[10] >> 29) & frc::M29;
-    vhi.v[3] = (uint32_t)(cols[10] >> 58);
-    return f9_norm_reduce(f9_add(vlo, f9_mul(vhi, fr_unpack(fr_const(frc::R2)))));
 }
 
 // The four input claims from the integers (same bounds as round 0 below): dot products of the
@@ -554,25 +510,6 @@ __device__ __forceinline__ void lin0_int_body(const LinArgs& a, const unsigned b
     Fr* pp = a.part + (uint64_t)bx * 4;
     if (threadIdx.x < 3) pp[threadIdx.x ? threadIdx.x + 1 : 0] = s;
     else if (threadIdx.x == 3) pp[1] = fr_zero();
-}
-
-// a0 + v0 (a2 - a0) in Montgomery form from the integers; k = (R^2, -R^2, v0 R^2, -v0 R^2),
-// canonical.  Four products below 2^58 per column; the result is normal and below 2 r.
-__device__ __forceinline__ F9 fold_ints(const F9* k, int64_t a0, int64_t a2) {
-    const int64_t d = a2 - a0;
-    const bool n0 = a0 < 0, nd = d < 0;
-    uint64_t cols[17];
-#pragma unroll
-    for (int c = 0; c < 17; ++c) cols[c] = 0;
-    F9 c0, cd;
-#pragma unroll
-    for (int i = 0; i < 9; ++i) {
-        c0.v[i] = n0 ? k[1].v[i] : k[0].v[i];
-        cd.v[i] = nd ? k[3].v[i] : k[2].v[i];
-    }
-    cols11_mac(cols, c0, n0 ? (uint64_t)0 - (uint64_t)a0 : (uint64_t)a0);
-    cols11_mac(cols, cd, nd ? (uint64_t)0 - (uint64_t)d : (uint64_t)d);
-    return f9_redc(cols);
 }
 
 // Round 1: v0 is bound on the way; the equality tables come from their two factors (H already

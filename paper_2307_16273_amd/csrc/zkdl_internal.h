@@ -155,8 +155,9 @@ int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, void* work_mem, 
 constexpr int ZK_HD_MIN_LOG = 14;
 // wsuf[t_last] built; fills wsuf[t_last - 1] .. wsuf[0], each from the one after it
 void zk_hadamard_suffix_tables(zkdl_ctx* ctx, const FrTab* wsuf, int t_last, int d, int p_idx);
-int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const FrTab* wsuf, void* work_mem, F9Tab eq_tail, int d, int p_idx,
-                   int finals_scal_base);
+// xi != nullptr: X0, X1 are int32 arrays on the device; the first two rounds read them and x is unused.
+int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const int32_t* const* xi, const FrTab* wsuf, void* work_mem,
+                   F9Tab eq_tail, int d, int p_idx, int finals_scal_base);
 // Queues the frame of a protocol header (label, n <= 8 little-endian u32 words); it is absorbed
 // by the next zk_launch_draw / zk_flush_frames, in stream order before everything that follows.
 void zk_absorb_words(zkdl_ctx* ctx, const char* label, const uint32_t* words, int n);

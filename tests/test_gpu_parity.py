@@ -368,6 +368,35 @@ def test_sumcheck_hadamard(lib, ctx, shape):
     assert tr.digest() == ots.digest()
 
 
+@pytest.mark.parametrize("shape,extreme", [((16384,), False), ((4, 64, 64), True), ((32, 64, 64), False), ((8192,), True)])
+def test_sumcheck_hadamard_int32_sources(lib, ctx, shape, extreme):
+    """int32 stacks wrapped in place: from 2^14 entries on the first two rounds read the integers
+    (products of the lines below 2^68, one reduction per thread) instead of converted tables."""
+    import torch
+    say(f"sumcheck_hadamard int32 shape={shape} extreme={extreme}")
+    rng = np.random.default_rng(23)
+    x0 = rng.integers(-2 ** 31, 2 ** 31, shape, dtype=np.int64).astype(np.int32)
+    x1 = rng.integers(-2 ** 31, 2 ** 31, shape, dtype=np.int64).astype(np.int32)
+    if extreme:       # the widest lines: 2 a1 - a0 = +-3 * 2^31 and their products, all sign patterns
+        n = x0.size
+        f0, f1 = x0.reshape(-1), x1.reshape(-1)
+        lo, hi = -2 ** 31, 2 ** 31 - 1
+        for i, (a0, a1, c0, c1) in enumerate([(lo, hi, lo, hi), (hi, lo, lo, hi), (lo, hi, hi, lo), (hi, lo, hi, lo),
+                                              (lo, lo, hi, hi), (0, lo, 0, lo), (hi, hi, hi, hi), (lo, lo, lo, lo)]):
+            f0[i], f0[i + n // 2], f1[i], f1[i + n // 2] = a0, a1, c0, c1
+            f0[n // 4 + i], f0[n // 4 + i + n // 2] = a1, a0      # the same in the pairs of round 1
+            f1[n // 4 + i], f1[n // 4 + i + n // 2] = c1, c0
+    a = lib.tensor_wrap_int(ctx, torch.from_numpy(x0).cuda(), shape)
+    b = lib.tensor_wrap_int(ctx, torch.from_numpy(x1).cuda(), shape)
+    tr = lib.Transcript(8)
+    got = lib.sumcheck_hadamard(ctx, a, b, tr)
+    ots = OracleTranscript(8)
+    buf, proof, pts = P.hadamard_prove(fr_array(x0), fr_array(x1), ots)
+    assert got["proof"] == buf and got["points"] == ots.challenges
+    assert got["claims"] == [proof.claim0, proof.finals[1], proof.finals[2]]
+    assert tr.digest() == ots.digest()
+
+
 def test_sumcheck_hadamard_full_size_by_properties(lib, ctx):
     """Hadamard product of two stacks of 2^24 int32 values (the size of the micro-benchmark's
     tables): the oracle's verifier replays all 24 rounds and ends in the library's transcript
