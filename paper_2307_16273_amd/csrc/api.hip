@@ -847,12 +847,16 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
     if (d >= ZK_HD_MIN_LOG) {
         // large: beta~(p, .) is never a folded table; the rounds take beta~(p_[t+1:], .) as weights
         const int t_tail = d - 10;
-        uint64_t suf_elems = 0;
-        for (int t = 0; t < t_tail; ++t) suf_elems += (uint64_t)1 << (d - t - 1);
+        // two int32 stacks are read as they are by the first two rounds: no conversion pass, and the
+        // first round takes its weights from two small tables instead of beta~(p_[1:], .)
+        const bool ints = X0->kind == TK_I32 && X1->kind == TK_I32;
+        const int t_first = ints ? 1 : 0;
+        const int split_lb = d - 1 < 14 ? d - 1 : 14;
+        const uint64_t split_h = (uint64_t)1 << (d - 1 - split_lb), split_l = (uint64_t)1 << split_lb;
+        uint64_t suf_elems = ints ? split_h + split_l : 0;
+        for (int t = t_first; t < t_tail; ++t) suf_elems += (uint64_t)1 << (d - t - 1);
         void* mem = zk_alloc(ctx, suf_elems * 32 + 2048 * 36 + zk_sumcheck_work_bytes(2, d));
         if (!mem) rc = ZKDL_ENOMEM;
-        // two int32 stacks are read as they are by the first two rounds: no conversion pass
-        const bool ints = X0->kind == TK_I32 && X1->kind == TK_I32;
         if (rc == ZKDL_OK && !ints) rc = as_fr(ctx, X0, &v0);
         if (rc == ZKDL_OK && !ints) rc = as_fr(ctx, X1, &v1);
         if (rc == ZKDL_OK) {
@@ -860,8 +864,15 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
             uint32_t* w = (uint32_t*)mem;
             for (int t = 0; t < t_tail; ++t) {
                 const uint64_t cnt = (uint64_t)1 << (d - t - 1);
-                wsuf[t] = make_tab(w, cnt);
-                w += 8 * cnt;
+                wsuf[t] = make_tab(t >= t_first ? w : nullptr, cnt);
+                if (t >= t_first) w += 8 * cnt;
+            }
+            FrTab split[2] = {make_tab(nullptr, 0), make_tab(nullptr, 0)};
+            if (ints) {
+                split[0] = make_tab(w, split_h);
+                w += 8 * split_h;
+                split[1] = make_tab(w, split_l);
+                w += 8 * split_l;
             }
             F9Tab eq_tail;
             eq_tail.p = w;
@@ -869,10 +880,16 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
             w += 9 * 2048;
             // the smallest table (10 variables) by doubling, every larger one from the one before
             rc = zk_build_beta(ctx, ctx->dev->chal + t_tail, d - t_tail, wsuf[t_tail - 1]);
-            if (rc == ZKDL_OK) zk_hadamard_suffix_tables(ctx, wsuf.data(), t_tail - 1, d, 0);
+            if (rc == ZKDL_OK) zk_hadamard_suffix_tables(ctx, wsuf.data(), t_tail - 1, t_first, d, 0);
+            if (rc == ZKDL_OK && ints) {
+                const BetaJob sj[2] = {{ctx->dev->chal + 1, d - 1 - split_lb, split[0]},
+                                       {ctx->dev->chal + d - split_lb, split_lb, split[1]}};
+                rc = zk_build_beta_many(ctx, sj, 2);
+            }
             FrTab xs[2] = {v0.tab, v1.tab};
             const int32_t* xi[2] = {(const int32_t*)X0->data, (const int32_t*)X1->data};
-            if (rc == ZKDL_OK) rc = zk_hadamard_eq(ctx, xs, ints ? xi : nullptr, wsuf.data(), w, eq_tail, d, 0, 0);
+            if (rc == ZKDL_OK)
+                rc = zk_hadamard_eq(ctx, xs, ints ? xi : nullptr, wsuf.data(), split, split_lb, w, eq_tail, d, 0, 0);
         }
         zkdl_fr tmp[3];
         int ids[3] = {0, 1, 2};

@@ -915,9 +915,9 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_hd_suffix_expand(FrTab src, FrTab 
     }
 }
 
-// wsuf[t] = beta~(p_[t+1:], .) for t = t_last - 1 .. 0 from wsuf[t_last] (each has one variable more)
-void zk_hadamard_suffix_tables(zkdl_ctx* ctx, const FrTab* wsuf, int t_last, int d, int p_idx) {
-    for (int t = t_last - 1; t >= 0; --t) {
+// wsuf[t] = beta~(p_[t+1:], .) for t = t_last - 1 .. t_first from wsuf[t_last] (each has one variable more)
+void zk_hadamard_suffix_tables(zkdl_ctx* ctx, const FrTab* wsuf, int t_last, int t_first, int d, int p_idx) {
+    for (int t = t_last - 1; t >= t_first; --t) {
         const uint64_t n = (uint64_t)1 << (d - t - 2);   // entries of wsuf[t + 1]
         const uint64_t want = (n + ZK_BLOCK - 1) / ZK_BLOCK;
         hipLaunchKernelGGL(k_hd_suffix_expand, dim3((unsigned)(want < 8192 ? want : 8192)), dim3(ZK_BLOCK), 0, ctx->stream,
@@ -947,7 +947,9 @@ struct HdIntArgs {
     const int32_t* x[2];
     F9Tab work[2];
     uint64_t m;        // pair indices this round
-    FrTab wsuf;        // beta~(p_[t+1:], .), m entries
+    FrTab wsuf;        // MODE 1: beta~(p_[2:], .), m entries
+    FrTab wH, wL;      // MODE 0: beta~(p_[1:], b) = wH[b >> lb] wL[b & (2^lb - 1)]
+    int lb;
     const Fr* chal;    // MODE 1: v_0
     Fr* part;          // block b: f(0), f(1), f(2) at part[3 b + x]
 };
@@ -999,15 +1001,37 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_hd_round_i32(HdIntArgs a) {
         for (int x = 0; x < 3; ++x)
 #pragma unroll
             for (int c = 0; c < 12; ++c) cols[x][c] = 0;
-        for (uint64_t b = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; b < m; b += (uint64_t)gridDim.x * blockDim.x) {
+        // sum_b wH[bh] wL[bl] q(b) = sum_bh wH[bh] (sum_bl wL[bl] q(b)): a block takes a contiguous range
+        // of pair indices, a thread keeps the inner sums as columns while its bh stays the same
+        // (wL is small and stays in the caches; no table of 2^(d-1) weights is read or built)
+#pragma unroll
+        for (int x = 0; x < 3; ++x) acc[x] = f9_zero();
+        const uint64_t per = ((m + gridDim.x - 1) / gridDim.x + ZK_BLOCK - 1) / ZK_BLOCK * ZK_BLOCK;
+        const uint64_t b0 = blockIdx.x * per, b1 = b0 + per < m ? b0 + per : m;
+        const uint64_t mask = ((uint64_t)1 << a.lb) - 1, none = ~(uint64_t)0;
+        uint64_t cur = none;
+        auto flush = [&](uint64_t bh) {
+            const F9 hv = fr_unpack(tab_ld(a.wH, bh));
+#pragma unroll
+            for (int x = 0; x < 3; ++x) {
+                acc[x] = f9_norm_reduce(f9_add(acc[x], f9_mul(hv, cols12_value(cols[x]))));
+#pragma unroll
+                for (int c = 0; c < 12; ++c) cols[x][c] = 0;
+            }
+        };
+        for (uint64_t b = b0 + threadIdx.x; b < b1; b += ZK_BLOCK) {
+            const uint64_t bh = b >> a.lb;
+            if (bh != cur) {
+                if (cur != none) flush(cur);
+                cur = bh;
+            }
             const int64_t a0 = a.x[0][b], a1 = a.x[0][b + m], c0 = a.x[1][b], c1 = a.x[1][b + m];
-            const F9 w = fr_unpack(tab_ld(a.wsuf, b));
+            const F9 w = fr_unpack(tab_ld(a.wL, b & mask));
             cols12_mac_prod(cols[0], w, a0, c0);
             cols12_mac_prod(cols[1], w, a1, c1);
             cols12_mac_prod(cols[2], w, 2 * a1 - a0, 2 * c1 - c0);
         }
-#pragma unroll
-        for (int x = 0; x < 3; ++x) acc[x] = cols12_value(cols[x]);
+        if (cur != none) flush(cur);
     } else {
         if (threadIdx.x < 4) {
             const Fr v0 = *a.chal, r2 = fr_const(frc::R2);
@@ -1044,9 +1068,10 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_hd_round_i32(HdIntArgs a) {
 
 // x: X0, X1 (packed, 2^d entries); wsuf[t], t < d - 10: beta~(p_[t+1:], .) with 2^(d-t-1) entries;
 // eq_tail: 2^11 work-table entries; p_idx: challenge index of p_0.  d >= ZK_HD_MIN_LOG.
-// xi != nullptr: both sources are int32 arrays (device) and x is not read.
-int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const int32_t* const* xi, const FrTab* wsuf, void* work_mem,
-                   F9Tab eq_tail, int d, int p_idx, int finals_scal_base) {
+// xi != nullptr: both sources are int32 arrays (device); x and wsuf[0] are not read, the first round
+// takes its weights as split[0][b >> split_lb] split[1][b & (2^split_lb - 1)].
+int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const int32_t* const* xi, const FrTab* wsuf, const FrTab* split,
+                   int split_lb, void* work_mem, F9Tab eq_tail, int d, int p_idx, int finals_scal_base) {
     constexpr int SC_TAIL_LOG = 10;
     if (d < ZK_HD_MIN_LOG || ctx->n_chal + d > ZK_MAX_CHAL) return ZKDL_EINVAL;
     zk_flush_frames(ctx);
@@ -1089,6 +1114,9 @@ int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const int32_t* const* xi, cons
             }
             ia.m = m;
             ia.wsuf = wsuf[t];
+            ia.wH = split[0];
+            ia.wL = split[1];
+            ia.lb = split_lb;
             ia.chal = fa.chal;
             ia.part = ctx->partials;
             // algorithmic bytes: the integers (2 or 4 per table), one weight, round 1 also the folded tables

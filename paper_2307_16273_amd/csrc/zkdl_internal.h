@@ -153,11 +153,13 @@ int zk_sumcheck_product(zkdl_ctx* ctx, int K, const FrTab* src, void* work_mem, 
 // packed; wsuf[t], t < d - 10: beta~(p_[t+1:], .), 2^(d-t-1) entries; eq_tail: 2^11 work-table
 // entries of scratch; work_mem: zk_sumcheck_work_bytes(2, d); p_idx: challenge index of p_0.
 constexpr int ZK_HD_MIN_LOG = 14;
-// wsuf[t_last] built; fills wsuf[t_last - 1] .. wsuf[0], each from the one after it
-void zk_hadamard_suffix_tables(zkdl_ctx* ctx, const FrTab* wsuf, int t_last, int d, int p_idx);
-// xi != nullptr: X0, X1 are int32 arrays on the device; the first two rounds read them and x is unused.
-int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const int32_t* const* xi, const FrTab* wsuf, void* work_mem,
-                   F9Tab eq_tail, int d, int p_idx, int finals_scal_base);
+// wsuf[t_last] built; fills wsuf[t_last - 1] .. wsuf[t_first], each from the one after it
+void zk_hadamard_suffix_tables(zkdl_ctx* ctx, const FrTab* wsuf, int t_last, int t_first, int d, int p_idx);
+// xi != nullptr: X0, X1 are int32 arrays on the device; the first two rounds read them, x and wsuf[0] are
+// unused and the first round's weights are split[0][b >> split_lb] * split[1][b & (2^split_lb - 1)]
+// (beta~ of the leading d - 1 - split_lb and of the last split_lb coordinates of p_[1:]).
+int zk_hadamard_eq(zkdl_ctx* ctx, const FrTab* x, const int32_t* const* xi, const FrTab* wsuf, const FrTab* split,
+                   int split_lb, void* work_mem, F9Tab eq_tail, int d, int p_idx, int finals_scal_base);
 // Queues the frame of a protocol header (label, n <= 8 little-endian u32 words); it is absorbed
 // by the next zk_launch_draw / zk_flush_frames, in stream order before everything that follows.
 void zk_absorb_words(zkdl_ctx* ctx, const char* label, const uint32_t* words, int n);
