@@ -949,6 +949,14 @@ struct HostSha {
     void u32(uint32_t v) {
         for (int b = 0; b < 4; ++b) ts::push_byte(s, (uint8_t)(v >> (8 * b)));
     }
+    // the digest as eight little-endian words (the form zk_absorb_words takes)
+    void digest_words(uint32_t out[8]) const {
+        uint8_t dg[32];
+        ts::digest(s, dg);
+        for (int i = 0; i < 8; ++i)
+            out[i] = (uint32_t)dg[4 * i] | ((uint32_t)dg[4 * i + 1] << 8) | ((uint32_t)dg[4 * i + 2] << 16) |
+                     ((uint32_t)dg[4 * i + 3] << 24);
+    }
 };
 
 static int upload_bytes(zkdl_ctx* ctx, const void* host, size_t n, void** dev_out) {
@@ -1026,12 +1034,8 @@ extern "C" int reindex_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, const i
         at += (size_t)lk[k] * 32;
     }
     hs.bytes(pts.data(), (size_t)ld * 32);
-    uint8_t dg[32];
-    ts::digest(hs.s, dg);
     uint32_t dgw[8];
-    for (int i = 0; i < 8; ++i)
-        dgw[i] = (uint32_t)dg[4 * i] | ((uint32_t)dg[4 * i + 1] << 8) | ((uint32_t)dg[4 * i + 2] << 16) |
-                 ((uint32_t)dg[4 * i + 3] << 24);
+    hs.digest_words(dgw);
 
     std::vector<uint32_t> row_off, ent, maps_flat;
     build_inverse_maps(K, maps, map_len, N, row_off, ent, maps_flat);
@@ -1163,12 +1167,8 @@ extern "C" int claims_merge_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int K, co
     hs.u32((uint32_t)d);
     hs.u32((uint32_t)K);
     hs.bytes(pts.data(), (size_t)K * d * 32);
-    uint8_t dg[32];
-    ts::digest(hs.s, dg);
     uint32_t dgw[8];
-    for (int i = 0; i < 8; ++i)
-        dgw[i] = (uint32_t)dg[4 * i] | ((uint32_t)dg[4 * i + 1] << 8) | ((uint32_t)dg[4 * i + 2] << 16) |
-                 ((uint32_t)dg[4 * i + 3] << 24);
+    hs.digest_words(dgw);
     int rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
     zk_absorb_words(ctx, "merge", dgw, 8);
@@ -1222,12 +1222,8 @@ extern "C" int claims_merge_stack_prove(zkdl_ctx* ctx, const zkdl_tensor* X, int
     hs.u32((uint32_t)D);
     hs.u32((uint32_t)K);
     hs.bytes(pts.data(), (size_t)K * d * 32);
-    uint8_t dg[32];
-    ts::digest(hs.s, dg);
     uint32_t dgw[8];
-    for (int i = 0; i < 8; ++i)
-        dgw[i] = (uint32_t)dg[4 * i] | ((uint32_t)dg[4 * i + 1] << 8) | ((uint32_t)dg[4 * i + 2] << 16) |
-                 ((uint32_t)dg[4 * i + 3] << 24);
+    hs.digest_words(dgw);
     int rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
     zk_absorb_words(ctx, "merge_stack", dgw, 8);
@@ -1311,11 +1307,7 @@ static int zkrelu_call(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint6
         // drawn ones would stand
         HostSha hs;
         hs.bytes(points, (size_t)4 * li * 32);
-        uint8_t dg[32];
-        ts::digest(hs.s, dg);
-        for (int i = 0; i < 8; ++i)
-            dgw[i] = (uint32_t)dg[4 * i] | ((uint32_t)dg[4 * i + 1] << 8) | ((uint32_t)dg[4 * i + 2] << 16) |
-                     ((uint32_t)dg[4 * i + 3] << 24);
+        hs.digest_words(dgw);
         if (li > 0) {
             rc = upload_bytes(ctx, points, (size_t)4 * li * 32, &d_pts);
             if (rc == ZKDL_OK) zk_launch_chal_set(ctx, ctx->n_chal, 4 * li, (const uint8_t*)d_pts, nullptr);
