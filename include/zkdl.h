@@ -48,12 +48,18 @@
  * Proof layout (all integers little-endian u32, all field elements zkdl_fr)
  *   SC block : "ZKSC", n_finals, degree, rounds, claim_0,
  *              rounds x (degree+1) evaluations g_t(0..degree), n_finals finals
- *   zkReLU   : "ZKRL", log2 D, Q, R, has_ga, 0, 0, 0, four input claims
+ *   zkReLU   : "ZKRL", log2 D, Q, R, has_ga, mode, 0, 0 (mode 0: all points drawn;
+ *              1, 2: the four points given, see zkrelu_prove_at), four input claims
  *              (Z, A, G_A, G_Z), SC block (degree 3, finals aux~(0,v,w),
  *              aux~(1,v,w), aux~(0,v,Q+R-1)), SC block of the merge (degree 2,
  *              finals aux~(k*,v,w*), E~(k*,w*))
  *   aggregate: "ZKAG", L, B, width, T', Q, R, 0, SC block forward, SC block
  *              gradA, SC block gradW, zkReLU proof
+ *   "ZKSF" (sumcheck_matmul_ft), "ZKRI" (reindex_prove), "ZKMG"
+ *   (claims_merge_prove), "ZKMS" (claims_merge_stack_prove) and "ZKAL"
+ *   (aggregate_prove_linked) are laid out at their declarations below.
+ * points_out also repeats, in front of the draws they precede, points that a
+ * call hands on from earlier challenges (aggregate_prove_linked).
  */
 #ifndef ZKDL_H
 #define ZKDL_H
