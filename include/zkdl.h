@@ -27,7 +27,12 @@
  *    on entry; on return the challenges drawn during the call are stored in
  *    draw order and *npoints is their number (ZKDL_ESMALL if too small).
  *  - proof / proof_len: *proof_len holds the capacity in bytes on entry and the
- *    bytes written on return.  ZKDL_ESMALL sets *proof_len to the size needed.
+ *    bytes written on return.  If the proof or the points buffer is too small
+ *    the call returns ZKDL_ESMALL with *proof_len and *npoints set to the sizes
+ *    needed and nothing else of the caller's changed: the transcript stays where
+ *    it was, so the same call with larger buffers gives the proof a verifier
+ *    replays.  proof == NULL with proof_len != NULL is that size query;
+ *    proof_len == NULL means the caller does not want the bytes.
  *
  * Transcript (this library's own format).  The transcript is one byte stream;
  * every value derived from it is a plain SHA-256 of an extension of it:

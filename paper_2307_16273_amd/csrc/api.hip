@@ -383,12 +383,19 @@ extern "C" int fr_tensor_upload(zkdl_ctx* ctx, const void* src, int dtype, int s
     }
     int kind = dtype == ZKDL_I32 ? TK_I32 : dtype == ZKDL_I64 ? TK_I64 : 3;
     zk_launch_convert(ctx, dsrc, kind, n, make_tab(t->data, n));
+    hipError_t e = hipSuccess;
     if (staged) {
         // the host buffer is pageable: make sure the copy has consumed it before returning
-        ZK_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        e = hipStreamSynchronize(ctx->stream);
         zk_free(ctx, staged);
     }
-    ZK_HIP(ctx, hipGetLastError());
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) {
+        ctx->last_hip = (int)e;
+        zk_free(ctx, t->data);
+        delete t;
+        return ZKDL_EHIP;
+    }
     *out = t;
     return ZKDL_OK;
 }
@@ -461,19 +468,18 @@ extern "C" int zkdl_tensor_download(zkdl_ctx* ctx, const zkdl_tensor* t, zkdl_fr
 // ---------------------------------------------------------------------------
 // call framing: transcript state to the device, proof and challenges back
 // ---------------------------------------------------------------------------
-struct HeaderPatch {
-    size_t off;
-    uint32_t words[8];
-    int n;
-};
-static thread_local std::vector<HeaderPatch> g_patches;
-
+// Header words of the proof are known on the host: they are kept in the context and written over the
+// device's proof bytes when the call ends.  A call that would need more than ZK_MAX_PATCHES of them
+// fails in call_end (patch_overflow).
 void zk_write_proof_words(zkdl_ctx* ctx, const uint32_t* words, int n) {
-    HeaderPatch p;
-    p.off = ctx->proof_len;
-    p.n = n;
-    for (int i = 0; i < n; ++i) p.words[i] = words[i];
-    g_patches.push_back(p);
+    if (ctx->n_patches < ZK_MAX_PATCHES) {
+        HeaderPatch& p = ctx->patches[ctx->n_patches++];
+        p.off = ctx->proof_len;
+        p.n = n;
+        for (int i = 0; i < n; ++i) p.words[i] = words[i];
+    } else {
+        ctx->patch_overflow = true;
+    }
     ctx->proof_len += 4 * (size_t)n;
 }
 
@@ -482,7 +488,8 @@ static int call_begin(zkdl_ctx* ctx, zkdl_transcript* tr) {
     ctx->n_chal = 0;
     ctx->proof_len = 0;
     ctx->pend_len = 0;
-    g_patches.clear();
+    ctx->n_patches = 0;
+    ctx->patch_overflow = false;
     // transcript state; error word and owed claim cleared
     memset(ctx->host_stage, 0, ZK_STATE_HEAD);
     {
@@ -497,11 +504,15 @@ static int call_begin(zkdl_ctx* ctx, zkdl_transcript* tr) {
     return ZKDL_OK;
 }
 
+// the proof bytes of the call that has just ended, in the staging buffer (header words not patched in)
+static const uint8_t* staged_proof(const zkdl_ctx* ctx) { return ((const DevState*)ctx->host_stage)->proof; }
+
 // rc_in: result of the enqueue phase; on failure the stream is drained and the caller's
 // transcript and buffers stay as they were
 static int call_end(zkdl_ctx* ctx, zkdl_transcript* tr, int rc_in, uint8_t* proof, size_t* proof_len,
                     zkdl_fr* points_out, size_t* npoints, const int* scal_ids, int n_scal,
                     zkdl_fr* scal_out) {
+    if (rc_in == ZKDL_OK && ctx->patch_overflow) rc_in = ZKDL_EINVAL;
     if (rc_in != ZKDL_OK) {
         ctx->pend_len = 0;
         ZK_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -522,33 +533,33 @@ static int call_end(zkdl_ctx* ctx, zkdl_transcript* tr, int rc_in, uint8_t* proo
     if (ctx->prof_on) prof_collect(ctx);
     const DevState* h = (const DevState*)hs;
     if (h->err & 1u) return ZKDL_ERANGE;
+    // A buffer that is too small (or a proof pointer of NULL, the query for the sizes) fails the call
+    // before anything of the caller's is touched: the sizes needed are reported, the transcript stays
+    // where it was, and the same call with larger buffers gives the proof the verifier replays.
+    const bool proof_small = proof_len && (!proof || *proof_len < ctx->proof_len);
+    const bool points_small = points_out && npoints && *npoints < (size_t)ctx->n_chal;
+    if (proof_len) *proof_len = ctx->proof_len;
+    if (npoints) *npoints = (size_t)ctx->n_chal;
+    if (proof_small || points_small) return ZKDL_ESMALL;
     for (int i = 0; i < 8; ++i) tr->s.h[i] = h->ts_state[i];
     tr->s.nblk = ((uint64_t)h->ts_nblk[1] << 32) | h->ts_nblk[0];
     tr->s.fill = h->ts_fill;
     for (uint32_t i = 0; i < 64; ++i)
         tr->s.buf[i] = i < h->ts_fill ? (uint8_t)(h->ts_buf[i >> 2] >> (24 - 8 * (i & 3))) : 0;
-    int rc = ZKDL_OK;
     if (proof_len) {
-        if (!proof || *proof_len < ctx->proof_len) {
-            rc = ZKDL_ESMALL;
-        } else {
-            memcpy(proof, h->proof, ctx->proof_len);
-            for (const HeaderPatch& p : g_patches)
-                for (int i = 0; i < p.n; ++i)
-                    for (int b = 0; b < 4; ++b) proof[p.off + 4 * i + b] = (uint8_t)(p.words[i] >> (8 * b));
+        memcpy(proof, h->proof, ctx->proof_len);
+        for (int k = 0; k < ctx->n_patches; ++k) {
+            const HeaderPatch& p = ctx->patches[k];
+            for (int i = 0; i < p.n; ++i)
+                for (int b = 0; b < 4; ++b) proof[p.off + 4 * i + b] = (uint8_t)(p.words[i] >> (8 * b));
         }
-        *proof_len = ctx->proof_len;
     }
-    if (points_out && npoints) {
-        if (*npoints < (size_t)ctx->n_chal) rc = ZKDL_ESMALL;
-        else memcpy(points_out, h->chal_le, 32 * (size_t)ctx->n_chal);
-    }
-    if (npoints) *npoints = (size_t)ctx->n_chal;
+    if (points_out && npoints) memcpy(points_out, h->chal_le, 32 * (size_t)ctx->n_chal);
     for (int i = 0; i < n_scal && scal_out; ++i) {
         Fr plain = fr_from_mont(h->scal[scal_ids[i]]);
         memcpy(scal_out[i].le, plain.v, 32);
     }
-    return rc;
+    return ZKDL_OK;
 }
 
 // ---------------------------------------------------------------------------
@@ -736,8 +747,8 @@ extern "C" int sumcheck_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_
     zkdl_fr tmp[3];
     int ids[3] = {0, 1, 2};
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 3, tmp);
-    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims && proof) {
-        memcpy(claims[0].le, proof + 16, 32);   // claim_0 = Y~(w, u0, u1)
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims) {
+        memcpy(claims[0].le, staged_proof(ctx) + 16, 32);   // claim_0 = Y~(w, u0, u1)
         claims[1] = tmp[1];
         claims[2] = tmp[2];
     }
@@ -821,8 +832,8 @@ extern "C" int sumcheck_matmul_ft(zkdl_ctx* ctx, const zkdl_tensor* X0, const zk
     zkdl_fr tmp[2];
     int ids[2] = {0, 1};
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 2, tmp);
-    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims && proof) {
-        memcpy(claims[0].le, proof + 16, 32);   // claim_0 = Y~(w, u0, u1)
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims) {
+        memcpy(claims[0].le, staged_proof(ctx) + 16, 32);   // claim_0 = Y~(w, u0, u1)
         claims[1] = tmp[0];
         claims[2] = tmp[1];
     }
@@ -894,8 +905,8 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
         zkdl_fr tmp[3];
         int ids[3] = {0, 1, 2};
         int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 3, tmp);
-        if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims && proof) {
-            memcpy(claims[0].le, proof + 16, 32);
+        if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims) {
+            memcpy(claims[0].le, staged_proof(ctx) + 16, 32);
             claims[1] = tmp[1];
             claims[2] = tmp[2];
         }
@@ -917,8 +928,8 @@ extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkd
     zkdl_fr tmp[3];
     int ids[3] = {0, 1, 2};
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 3, tmp);
-    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims && proof) {
-        memcpy(claims[0].le, proof + 16, 32);
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims) {
+        memcpy(claims[0].le, staged_proof(ctx) + 16, 32);
         claims[1] = tmp[1];
         claims[2] = tmp[2];
     }
@@ -1315,7 +1326,7 @@ static int zkrelu_call(zkdl_ctx* ctx, const int64_t* Z, const int64_t* GA, uint6
     }
     const int64_t* zd = Z;
     const int64_t* gd = GA;
-    if (!src_on_device) {
+    if (rc == ZKDL_OK && !src_on_device) {
         rc = stage_ints(ctx, Z, D, &zs);
         zd = (const int64_t*)zs;
         if (rc == ZKDL_OK && GA) {

@@ -188,17 +188,7 @@ static FinArgs zk_fin_args(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint
 
 void zk_launch_finalise(zkdl_ctx* ctx, int nblk, int npts, int chal_idx, uint32_t proof_off, int first,
                         uint32_t claim_off, int derive1) {
-    FinArgs fa;
-    fa.part = ctx->partials;
-    fa.nblk = nblk;
-    fa.npts = npts;
-    fa.st = ctx->dev;
-    fa.chal_idx = chal_idx;
-    fa.proof_off = proof_off;
-    fa.first = first;
-    fa.claim_off = claim_off;
-    fa.claim_copy_off = 0;
-    fa.derive1 = derive1;
+    FinArgs fa = zk_fin_args(ctx, nblk, npts, chal_idx, proof_off, first, claim_off, derive1);
     zk_prof_begin(ctx, ZKDL_PROF_FINALISE, 32.0 * npts);
     hipLaunchKernelGGL(k_sc_finalise, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, fa);
     zk_prof_end(ctx);

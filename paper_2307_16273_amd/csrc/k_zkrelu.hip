@@ -102,8 +102,9 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_zk_split_fold(SplitEq src, SplitEq
 }
 
 __device__ __forceinline__ int64_t rescale_half_up(int64_t x, int r_bits) {
-    // floor((x + 2^(R-1)) / 2^R) without overflow
-    return ((x >> (r_bits - 1)) + 1) >> 1;
+    // floor((x + 2^(R-1)) / 2^R) as the recomposition Z' = aux[R:Q+R] . s_Q + aux[R-1] (Sec. 3.1) writes it:
+    // the value above bit R plus bit R-1; no sum that could leave the 64-bit range (R = 1, x = INT64_MAX)
+    return (x >> r_bits) + ((x >> (r_bits - 1)) & 1);
 }
 
 __device__ __forceinline__ bool in_range(int64_t x, int nbits) {

@@ -53,6 +53,13 @@ struct zkdl_transcript {
     ts::State s;
 };
 
+constexpr int ZK_MAX_PATCHES = 64;       // proof-header records of one call
+struct HeaderPatch {
+    size_t off;
+    uint32_t words[8];
+    int n;
+};
+
 struct zkdl_ctx {
     int device;
     hipStream_t stream;
@@ -65,6 +72,9 @@ struct zkdl_ctx {
     // per-call bookkeeping (host mirrors of device cursors)
     int n_chal;
     size_t proof_len;
+    HeaderPatch patches[ZK_MAX_PATCHES];
+    int n_patches;
+    bool patch_overflow;
     // transcript frames known on the host (protocol headers) that the next transcript
     // kernel absorbs before anything else
     uint8_t pend[ZK_PEND_CAP];
