@@ -82,7 +82,8 @@ typedef enum {
     ZKDL_ERANGE = -2, /* a zkReLU input is not a (Q+R)-bit signed integer (Theorem completeness) */
     ZKDL_ENOMEM = -3, /* device or host allocation failed */
     ZKDL_EHIP = -4,   /* a HIP runtime call failed */
-    ZKDL_ESMALL = -5  /* an output buffer is too small */
+    ZKDL_ESMALL = -5, /* an output buffer is too small */
+    ZKDL_ETOOBIG = -6 /* the input exceeds the fixed work memory of an allocation-free entry point */
 } zkdl_err;
 
 typedef enum { ZKDL_I32 = 0, ZKDL_I64 = 1, ZKDL_FR_LE = 2 } zkdl_dtype;
@@ -157,6 +158,23 @@ int mle_partial_eval(zkdl_ctx* ctx, const zkdl_tensor* t, int axis_lo, int axis_
 int sumcheck_product(zkdl_ctx* ctx, const zkdl_tensor* const* tables, int K, zkdl_transcript* tr,
                      uint8_t* proof, size_t* proof_len, zkdl_fr* finals, zkdl_fr* points_out,
                      size_t* npoints);
+
+/* sumcheck_product_noalloc: sumcheck_product for callers that cannot allocate device memory while
+ * they run - code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, transcript, proof bytes and results as sumcheck_product.  The folded tables live
+ * in a static device array of the library (3 x 2^(ZKDL_NOALLOC_MAX_LOG2 - 1) x 36 bytes = 13.5 MiB,
+ * held by every GPU the library runs on until the process ends) whose address on the context's
+ * device is taken when the context is created; the call itself makes no hipMalloc / hipFree and no
+ * other allocation, on the device or the host.  Limits: every table an Fr tensor (an integer view
+ * would need a converted copy: ZKDL_EINVAL), at most 2^ZKDL_NOALLOC_MAX_LOG2 entries per table
+ * (ZKDL_ETOOBIG beyond, nothing is enqueued and the transcript is untouched), per-kernel timing
+ * switched off (ZKDL_EINVAL).  All calls on one GPU share the one array: calls that overlap on a GPU,
+ * from different contexts or streams, race; calls on one context follow each other on its stream and
+ * need nothing cleared in between. */
+#define ZKDL_NOALLOC_MAX_LOG2 18
+int sumcheck_product_noalloc(zkdl_ctx* ctx, const zkdl_tensor* const* tables, int K, zkdl_transcript* tr,
+                             uint8_t* proof, size_t* proof_len, zkdl_fr* finals, zkdl_fr* points_out,
+                             size_t* npoints);
 
 /* sumcheck_matmul: Eq. exm-matmul-batched,
  *   Y~(w,u0,u1) = sum_n sum_i beta~(w,n) X0~(n,u0,i) X1~(n,i,u1)

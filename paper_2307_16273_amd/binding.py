@@ -9,7 +9,7 @@ _LIB = None
 
 ZKDL_I32, ZKDL_I64, ZKDL_FR_LE = 0, 1, 2
 ERRORS = {0: "ok", -1: "ZKDL_EINVAL", -2: "ZKDL_ERANGE", -3: "ZKDL_ENOMEM", -4: "ZKDL_EHIP",
-          -5: "ZKDL_ESMALL"}
+          -5: "ZKDL_ESMALL", -6: "ZKDL_ETOOBIG"}
 
 EXPORTED_SYMBOLS = [
     "zkdl_ctx_create", "zkdl_ctx_destroy", "zkdl_last_hip_error", "zkdl_strerror", "zkdl_ctx_trim",
@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "zkdl_transcript_challenge", "zkdl_transcript_digest",
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
-    "mle_partial_eval", "sumcheck_product", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_hadamard",
+    "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_hadamard",
     "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read",
 ]
@@ -69,6 +69,7 @@ def load_library():
         "zkdl_tensor_ndim": [vp], "zkdl_tensor_download": [vp, vp, vp], "zkdl_tensor_free": [vp, vp],
         "mle_partial_eval": [vp, vp, i, i, vp, sz, pp],
         "sumcheck_product": [vp, pp, i, vp, vp, psz, vp, vp, psz],
+        "sumcheck_product_noalloc": [vp, pp, i, vp, vp, psz, vp, vp, psz],
         "sumcheck_matmul": [vp, vp, vp, i, i, vp, vp, psz, vp, vp, psz],
         "sumcheck_matmul_ft": [vp, vp, vp, i, i, vp, vp, psz, vp, vp, psz],
         "sumcheck_hadamard": [vp, vp, vp, vp, vp, psz, vp, vp, psz],
@@ -297,12 +298,14 @@ class _Outputs:
                     points=_split_fr(self.points.raw, self.npoints.value))
 
 
-def sumcheck_product(ctx, tables, tr):
+def sumcheck_product(ctx, tables, tr, noalloc=False):
+    """noalloc: the entry point that allocates nothing (Fr tables of at most 2^18 entries)."""
     k = len(tables)
     arr = (C.c_void_p * k)(*[t.handle for t in tables])
     o = _Outputs(k)
-    _check(load_library().sumcheck_product(ctx.handle, arr, k, tr.handle, o.proof, C.byref(o.proof_len),
-                                           o.claims, o.points, C.byref(o.npoints)), "sumcheck_product", ctx)
+    name = "sumcheck_product_noalloc" if noalloc else "sumcheck_product"
+    _check(getattr(load_library(), name)(ctx.handle, arr, k, tr.handle, o.proof, C.byref(o.proof_len),
+                                         o.claims, o.points, C.byref(o.npoints)), name, ctx)
     return o.result()
 
 

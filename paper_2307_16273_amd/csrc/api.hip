@@ -2,6 +2,7 @@
 // orchestration of each proof (which kernels run, in which order, on the
 // context's stream).  See include/zkdl.h for the contract of every entry point.
 #include <string.h>
+#include <mutex>
 #include <new>
 
 #include "zkdl_internal.h"
@@ -51,6 +52,34 @@ extern "C" int zkdl_ctx_trim(zkdl_ctx* ctx) {
     for (auto& kv : ctx->free_blocks) (void)hipFree(kv.second);
     ctx->free_blocks.clear();
     return ZKDL_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Work memory of sumcheck_product_noalloc: the folded tables of a product sumcheck of up to three
+// tables of 2^ZKDL_NOALLOC_MAX_LOG2 entries (zk_sumcheck_work_bytes).  Every GPU the library runs on
+// holds its own copy at its own address for the life of the process; the name below is only a handle
+// for hipGetSymbolAddress, the address it yields is what kernels and copies are given.
+// ---------------------------------------------------------------------------
+constexpr size_t ZK_NOALLOC_SCRATCH_BYTES = (size_t)3 * ((size_t)1 << (ZKDL_NOALLOC_MAX_LOG2 - 1)) * 36;
+static __device__ __align__(256) unsigned char scratch[ZK_NOALLOC_SCRATCH_BYTES];
+
+constexpr int ZK_MAX_DEVICES = 64;
+static void* g_scratch_addr[ZK_MAX_DEVICES];   // per device, set once under g_scratch_lock
+static std::mutex g_scratch_lock;
+
+// the address of `scratch` on `device`, which must be the current device
+static hipError_t static_scratch_address(int device, void** out) {
+    if (device < 0 || device >= ZK_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_addr[device]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_addr[device] = p;
+    }
+    *out = g_scratch_addr[device];
+    return hipSuccess;
 }
 
 // ---------------------------------------------------------------------------
@@ -113,6 +142,7 @@ extern "C" const char* zkdl_strerror(int err) {
         case ZKDL_ENOMEM: return "out of memory";
         case ZKDL_EHIP: return "HIP runtime error";
         case ZKDL_ESMALL: return "output buffer too small";
+        case ZKDL_ETOOBIG: return "input larger than the allocation-free entry point's static work memory";
         default: return "unknown error";
     }
 }
@@ -139,6 +169,8 @@ extern "C" int zkdl_ctx_create(zkdl_ctx** out, int device, void* hip_stream) {
         ctx->prof_launches[i] = 0;
     }
     hipError_t e = hipSetDevice(device);
+    ctx->static_scratch = nullptr;
+    if (e == hipSuccess) e = static_scratch_address(device, &ctx->static_scratch);
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->dev, sizeof(DevState));
     if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->host_stage, sizeof(DevState), hipHostMallocDefault);
     if (e == hipSuccess)
@@ -658,6 +690,36 @@ extern "C" int sumcheck_product(zkdl_ctx* ctx, const zkdl_tensor* const* tables,
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, K, finals);
     zk_free(ctx, wmem);
     for (int k = 0; k < K; ++k) zk_free(ctx, views[k].scratch);
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
+// sumcheck_product with its work tables in the library's static device array: no allocation of any
+// kind between entry and return (the context's state block, partial-sum slots and pinned staging
+// buffer were allocated when the context was created).
+extern "C" int sumcheck_product_noalloc(zkdl_ctx* ctx, const zkdl_tensor* const* tables, int K,
+                                        zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+                                        zkdl_fr* finals, zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !tables || !tr || K < 1 || K > 3) return ZKDL_EINVAL;
+    for (int k = 0; k < K; ++k) {
+        if (!tables[k] || tables[k]->numel != tables[0]->numel) return ZKDL_EINVAL;
+        if (tables[k]->kind != TK_FR) return ZKDL_EINVAL;   // an integer view would need a converted copy
+    }
+    if (ctx->prof_on) return ZKDL_EINVAL;                   // per-kernel timing creates events
+    const uint64_t n = tables[0]->numel;
+    const int d = ilog2_u64(n);
+    if (d > ZKDL_NOALLOC_MAX_LOG2) return ZKDL_ETOOBIG;
+    if (zk_sumcheck_work_bytes(K, d) > ZK_NOALLOC_SCRATCH_BYTES || !ctx->static_scratch) return ZKDL_ETOOBIG;
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    uint32_t hdr[2] = {(uint32_t)K, (uint32_t)d};
+    zk_absorb_words(ctx, "sumcheck_product", hdr, 2);
+    FrTab src[3];
+    for (int k = 0; k < K; ++k) src[k] = make_tab(tables[k]->data, tables[k]->numel);
+    // every work-table entry a round reads was written by the round before it in this call (the first
+    // round reads the inputs only), so what an earlier call left in the array is never seen
+    rc = zk_sumcheck_product(ctx, K, src, ctx->static_scratch, d, 0);
+    int ids[3] = {0, 1, 2};
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, K, finals);
     return rc != ZKDL_OK ? rc : rc2;
 }
 

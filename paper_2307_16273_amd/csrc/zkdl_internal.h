@@ -67,6 +67,7 @@ struct zkdl_ctx {
     DevState* dev;            // device
     uint8_t* host_stage;      // pinned host staging (sizeof(DevState))
     Fr* partials;             // device: ZK_MAX_PART_BLOCKS * ZK_MAX_EVALS * 2 partial sums
+    void* static_scratch;     // device address, on this context's device, of the library's static work memory
     std::multimap<size_t, void*> free_blocks;
     std::map<void*, size_t> live_blocks;
     // per-call bookkeeping (host mirrors of device cursors)
