@@ -40,6 +40,16 @@ def traffic_from_profiles():
         return None
 
 
+def valu_busy_from_profiles():
+    """VALU issue-slot occupancy of the fused round kernel from the committed counter summary (rocprofv3 --pmc)."""
+    path = os.path.join(ROOT, "profiles", "valu_lds_counters_bench_workloads.txt")
+    try:
+        m = re.search(r"^k_sc_round<3,1>\s+\S+\s+\S+\s+([0-9.]+)%", open(path).read(), re.M)
+        return float(m.group(1)) / 100.0 if m else None
+    except OSError:
+        return None
+
+
 def cpu_baseline(log2_size):
     """The CPU oracle, as it stands, on the same workload: its C tier (OpenMP, all host cores)
     at the full size, and the Python-integer tier (one core) on a reduced sample."""
@@ -74,7 +84,42 @@ def cpu_baseline(log2_size):
     dt = time.perf_counter() - t0
     out["python_tier"] = {"value": (3 * n + side * side) / dt, "unit": "Fr elements/s", "cores": 1,
                           "sample": f"3 tables of 2^{log2_size} and a {side}x{side} matrix, {dt:.1f} s on one core"}
+    out["cpu_model"] = cpu_model()
     return out
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline_aggregate():
+    """The oracle's C tier proving the 8 x 1024^2, batch-64 window (the one behind 'proof ms per
+    batch-64 8-layer step'): the whole window on all host threads, and, as the one-core figure, a
+    one-layer window of the same width and batch (an eighth of the rows; the whole window would take
+    minutes on one core)."""
+    from oracle import c_oracle
+    from workloads import fcnn_window, CONFIG_SEED
+    wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)
+    nthreads = c_oracle.threads()
+    t0 = time.perf_counter()
+    c_oracle.aggregate_prove(wit, c_oracle.Transcript(CONFIG_SEED + 3))
+    t_all = time.perf_counter() - t0
+    one = fcnn_window(CONFIG_SEED + 3, n_layers=1, width=1024, batch=64, steps=1)
+    c_oracle.set_threads(1)
+    t0 = time.perf_counter()
+    c_oracle.aggregate_prove(one, c_oracle.Transcript(CONFIG_SEED + 3))
+    t_one = time.perf_counter() - t0
+    c_oracle.set_threads(nthreads)
+    return {"proof_ms_batch64_8layer_step": 1e3 * t_all, "cores": nthreads, "kind": "oracle (C tier)",
+            "one_core": {"proof_ms": 1e3 * t_one, "cores": 1,
+                         "sample": "one layer of 1024 x 1024, batch 64 (2^16 zkReLU rows: an eighth of the window)"},
+            "cpu_model": cpu_model()}
 
 
 def main():
@@ -149,6 +194,11 @@ def main():
     sc_med, sc_min = timed(lambda: zk.sumcheck_product(ctx, tabs, zk.Transcript(5)), 5)
     pe_med, pe_min = timed(lambda: zk.mle_partial_eval(ctx, mat, 0, 1, point).free(), 5)
 
+    # the machine's own rates, measured now on this GPU: a streaming copy, independent v_mad_u64_u32
+    # chains in registers, the field multiplier in registers
+    copy_gbs = max(ctx.selfbench("copy", 1 << 30) for _ in range(3)) / 1e9
+    mad_tps = max(ctx.selfbench("mad", 1 << 12) for _ in range(3)) / 1e12
+    modmul_gps = max(ctx.selfbench("modmul", 1 << 10) for _ in range(3)) / 1e9
     fused = prof["sc_round_fused"]
     ach = fused["bytes"] / (fused["ms"] * 1e-3) / 1e9 if fused["ms"] > 0 else 0.0
     pairs = fused["bytes"] / 576.0            # K = 3: 576 algorithmic bytes per pair index
@@ -159,7 +209,13 @@ def main():
         "traffic": traffic_from_profiles(),
         "launches": fused["launches"], "avg_launch_us": 1e3 * fused["ms"] / max(fused["launches"], 1),
         "algorithmic_bytes_per_launch": fused["bytes"] / max(fused["launches"], 1),
-        "alu": {"achieved": mad_rate, "peak": MAD_PEAK_T, "unit": "Tmad/s", "frac": mad_rate / MAD_PEAK_T},
+        "alu": {"achieved": mad_rate, "peak": MAD_PEAK_T, "unit": "Tmad/s", "frac": mad_rate / MAD_PEAK_T,
+                "measured_mad_peak": mad_tps, "frac_of_measured_mad_peak": mad_rate / mad_tps if mad_tps else None,
+                "modmul_per_s": mad_rate * 1e12 / MADS_PER_MODMUL,
+                "measured_modmul_peak_per_s": modmul_gps * 1e9,
+                "frac_of_measured_modmul_peak": mad_rate * 1e3 / MADS_PER_MODMUL / modmul_gps if modmul_gps else None},
+        "valu_issue_busy_from_counters": valu_busy_from_profiles(),
+        "measured_copy_GBps": copy_gbs, "frac_of_measured_copy": ach / copy_gbs if copy_gbs else None,
         "other_kernels": {k: {"launches": v["launches"], "ms": v["ms"],
                               "GBps": (v["bytes"] / (v["ms"] * 1e-3) / 1e9 if v["ms"] > 0 else 0.0)}
                           for k, v in prof.items() if k != "sc_round_fused" and v["launches"]},
@@ -234,6 +290,8 @@ def main():
             ctx.trim()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_log2_size)
+        if not args.no_aggregate:
+            out["cpu_baseline"]["aggregate_8x1024_b64"] = cpu_baseline_aggregate()
     print(json.dumps(out))
 
 

@@ -365,6 +365,21 @@ int zkdl_ctx_profile_reset(zkdl_ctx* ctx);
 int zkdl_ctx_profile_read(zkdl_ctx* ctx, int cls, uint64_t* launches, double* total_ms,
                           double* total_bytes);
 
+/* ---- machine probes (for callers that report roofline fractions; paper-independent) ----
+ * Runs one probe kernel on the context's stream (after an untimed warm-up launch) and returns the
+ * work it did and the time HIP events measured around it:
+ *   ZKDL_SB_COPY    a device-to-device copy of `work` bytes (multiple of 16, at most 2^34);
+ *                   *units = bytes read + bytes written = 2 work
+ *   ZKDL_SB_MAD     2048 blocks x 256 threads, each running `work` x 64 multiply-adds of 32 x 32 + 64
+ *                   bits in 16 independent register chains; *units = multiply-adds
+ *   ZKDL_SB_MODMUL  the same grid, each thread `work` x 2 Montgomery products of the field
+ *                   multiplier in registers; *units = products
+ * work <= 2^24 for the last two.  The copy takes its two buffers from the context's allocator. */
+#define ZKDL_SB_COPY 0
+#define ZKDL_SB_MAD 1
+#define ZKDL_SB_MODMUL 2
+int zkdl_selfbench(zkdl_ctx* ctx, int what, uint64_t work, double* units, double* seconds);
+
 /* ---- host-side self checks (no GPU needed) -------------------------------- */
 /* out = a * b mod r computed by the library's Montgomery code on the host. */
 int zkdl_host_fr_mul(const zkdl_fr* a, const zkdl_fr* b, zkdl_fr* out);

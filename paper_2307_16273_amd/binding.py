@@ -20,7 +20,7 @@ EXPORTED_SYMBOLS = [
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
     "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_hadamard",
     "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
-    "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read",
+    "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read", "zkdl_selfbench",
 ]
 
 PROF_CLASSES = {"sc_round_fused": 0, "sc_round_first": 1, "partial_eval": 2, "zk_bin": 3, "zk_lin": 4,
@@ -83,6 +83,7 @@ def load_library():
         "zkdl_host_fr_mul": [vp, vp, vp], "zkdl_selfcheck_constants": [],
         "zkdl_ctx_profile_enable": [vp, i], "zkdl_ctx_profile_reset": [vp],
         "zkdl_ctx_profile_read": [vp, i, C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
+        "zkdl_selfbench": [vp, i, u64, C.POINTER(C.c_double), C.POINTER(C.c_double)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -136,6 +137,14 @@ class Context:
                    "zkdl_ctx_profile_read", self)
             out[name] = dict(launches=n.value, ms=ms.value, bytes=by.value)
         return out
+
+    def selfbench(self, what, work):
+        """One machine probe ("copy": bytes, "mad" / "modmul": loop count); returns units per second."""
+        units, secs = C.c_double(), C.c_double()
+        code = {"copy": 0, "mad": 1, "modmul": 2}[what]
+        _check(load_library().zkdl_selfbench(self.handle, code, int(work), C.byref(units), C.byref(secs)),
+               "zkdl_selfbench", self)
+        return units.value / secs.value
 
     def trim(self):
         _check(load_library().zkdl_ctx_trim(self.handle), "zkdl_ctx_trim", self)
