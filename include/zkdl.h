@@ -317,11 +317,50 @@ typedef struct {
     const int64_t* GA;
 } zkdl_fcnn_witness;
 
+/* What a window's proof leaves to be opened against commitments (Protocol zkdl, the proof-of-
+ * evaluation line): claims "the multilinear extension of tensor T at point p is y".  A point is given
+ * by reference into points_out: the concatenation of points_out[seg_off[s] .. seg_off[s] + seg_len[s])
+ * for s < nseg, in the tensor's own axis order (stack index, rows, columns; for aux: slice k, row,
+ * bit).  Stacks have N = T' L slots, slot n = t L + (l-1). */
+typedef enum {
+    ZKDL_T_A = 0,        /* A  [N,B,width]: input of layer l */
+    ZKDL_T_W = 1,        /* W  [N,width,width] */
+    ZKDL_T_GZ = 2,       /* GZ [N,B,width]: gradient of Z^(l) */
+    ZKDL_T_Z = 3,        /* Z = A W of every layer [N,B,width] (the forward family's product) */
+    ZKDL_T_ZR = 4,       /* Zr: Z where a ReLU follows, zero in last-layer slots (zkReLU's input) */
+    ZKDL_T_GA = 5,       /* GA [N,B,width]: the gradA family's product = zkReLU's second input */
+    ZKDL_T_GW = 6,       /* GW = A^T GZ [N,width,width] (the gradW family's product) */
+    ZKDL_T_A_RELU = 7,   /* ReLU outputs (1 - sign) Z', slot (t,l) = input of layer l+1, zero in last-layer slots */
+    ZKDL_T_GZ_RELU = 8,  /* (1 - sign) G_A': GZ with the last-layer slots zero */
+    ZKDL_T_GZ_NEXT = 9,  /* GZ with slot (t,l) <- slot (t,l+1), zero in last-layer slots */
+    ZKDL_T_W_NEXT = 10,  /* W with slot (t,l) <- slot (t,l+1), zero in last-layer slots; point in W's (in, out) order */
+    ZKDL_T_AUX = 11,     /* aux [2, N B width, J]: the bit decompositions of Zr and GA */
+    ZKDL_T_Z_LAST = 12,  /* Z of the last layer [T',B,width] */
+    ZKDL_T_GZ_LAST = 13  /* GZ of the last layer [T',B,width] */
+} zkdl_claim_tensor;
+#define ZKDL_CLAIM_MAX_SEGS 4
+typedef struct {
+    uint32_t tensor; /* zkdl_claim_tensor */
+    uint32_t nseg;
+    uint32_t seg_off[ZKDL_CLAIM_MAX_SEGS];
+    uint32_t seg_len[ZKDL_CLAIM_MAX_SEGS];
+    zkdl_fr value;
+} zkdl_claim;
+#define ZKDL_AGGREGATE_NCLAIMS 14
+#define ZKDL_AGGREGATE_LINKED_NCLAIMS 7
+
 /* aggregate_prove: forward (Z = A W), gradA (G_A = G_Z^(l+1) W^(l+1)T, last
  * slot of each step zero), gradW (G_W = A^T G_Z) matmul sumchecks and zkReLU on
- * (Zr, GA), in that order on one transcript. */
+ * (Zr, GA), in that order on one transcript.
+ * claims_out (host, may be NULL; *nclaims = capacity on entry, ZKDL_AGGREGATE_NCLAIMS needed, else
+ * ZKDL_ESMALL before anything runs): the claims the four sumchecks leave side by side, in proof order -
+ * forward: Z at (w,u0,u1), A at (v_n,u0,v_i), W at (v_n,v_i,u1); gradA: GA at (w,u0,u1), GZ_NEXT at
+ * (v_n,u0,v_i), W_NEXT at (v_n,u1,v_i); gradW: GW at (w,u0,u1), A at (v_n,v_i,u0), GZ at (v_n,v_i,u1);
+ * zkReLU: ZR at u_Z, A_RELU at u_A, GA at u_GA, GZ_RELU at u_GZ, AUX at (k*, v, w*).
+ * The segments index points_out, which must then be given as well (ZKDL_EINVAL otherwise). */
 int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
-                    size_t* proof_len, zkdl_fr* points_out, size_t* npoints);
+                    size_t* proof_len, zkdl_fr* points_out, size_t* npoints, zkdl_claim* claims_out,
+                    size_t* nclaims);
 
 /* aggregate_prove_linked: the same four families with their claims chained (Sec. 3.2: the
  * claims zkReLU starts from are left by the other operations' sumchecks; Sec. 4, Eq.
@@ -344,8 +383,13 @@ int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* 
  * prover.  Proof: "ZKAL" header (L, B, width, T, Q, R, 0), three SC blocks, the zkReLU
  * proof, three "ZKRI" proofs, two "ZKMS" proofs.  points_out: every challenge in order; the 4 log2(N B width)
  * coordinates given to zkReLU are repeated in front of its own draws. */
+/* claims_out (as for aggregate_prove; ZKDL_AGGREGATE_LINKED_NCLAIMS entries): the one claim per stack that is
+ * left - A, W, GZ, Z_LAST, GZ_LAST, GW, AUX.  The values on Z_LAST and GZ_LAST are the last layer's share
+ * divided by beta~ of the layer coordinates at L-1, as the verifier computes them (reported as zero in the
+ * event, of probability about 2^-255 per coordinate, that this factor is zero). */
 int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
-                           size_t* proof_len, zkdl_fr* points_out, size_t* npoints);
+                           size_t* proof_len, zkdl_fr* points_out, size_t* npoints, zkdl_claim* claims_out,
+                           size_t* nclaims);
 
 /* ---- per-kernel timing (for callers that measure; paper-independent) -------
  * While enabled, the launches of the kernel classes below are bracketed by HIP

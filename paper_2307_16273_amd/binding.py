@@ -41,6 +41,15 @@ class FcnnWitness(C.Structure):
                 ("GA", C.c_void_p)]
 
 
+class Claim(C.Structure):
+    _fields_ = [("tensor", C.c_uint32), ("nseg", C.c_uint32), ("seg_off", C.c_uint32 * 4),
+                ("seg_len", C.c_uint32 * 4), ("value", C.c_uint8 * 32)]
+
+
+CLAIM_TENSORS = ["A", "W", "GZ", "Z", "ZR", "GA", "GW", "A_RELU", "GZ_RELU", "GZ_NEXT", "W_NEXT", "AUX",
+                 "Z_LAST", "GZ_LAST"]
+
+
 def library_path():
     return os.path.join(_HERE, "libzkdl.so")
 
@@ -78,8 +87,8 @@ def load_library():
         "claims_merge_stack_prove": [vp, vp, i, pp, vp, vp, psz, vp, vp, psz],
         "zkrelu_prove": [vp, vp, vp, u64, i, i, i, vp, vp, psz, vp, vp, psz],
         "zkrelu_prove_at": [vp, vp, vp, u64, i, i, i, vp, vp, vp, psz, vp, vp, psz],
-        "aggregate_prove": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
-        "aggregate_prove_linked": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
+        "aggregate_prove": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz, vp, psz],
+        "aggregate_prove_linked": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz, vp, psz],
         "zkdl_host_fr_mul": [vp, vp, vp], "zkdl_selfcheck_constants": [],
         "zkdl_ctx_profile_enable": [vp, i], "zkdl_ctx_profile_reset": [vp],
         "zkdl_ctx_profile_read": [vp, i, C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
@@ -415,9 +424,18 @@ def aggregate_prove(ctx, wit, tr, linked=False):
                     wit["GA"].data_ptr())
     o = _Outputs(0)
     name = "aggregate_prove_linked" if linked else "aggregate_prove"
+    claims = (Claim * 16)()
+    nclaims = C.c_size_t(16)
     _check(getattr(load_library(), name)(ctx.handle, C.byref(w), tr.handle, o.proof, C.byref(o.proof_len),
-                                         o.points, C.byref(o.npoints)), name, ctx)
-    return o.result()
+                                         o.points, C.byref(o.npoints), claims, C.byref(nclaims)), name, ctx)
+    out = o.result()
+    pts = out["points"]
+    out["claims_left"] = [
+        dict(tensor=CLAIM_TENSORS[c.tensor],
+             point=[x for s in range(c.nseg) for x in pts[c.seg_off[s]:c.seg_off[s] + c.seg_len[s]]],
+             value=int.from_bytes(bytes(c.value), "little"))
+        for c in claims[:nclaims.value]]
+    return out
 
 
 def host_fr_mul(a, b):

@@ -2,8 +2,10 @@
 // orchestration of each proof (which kernels run, in which order, on the
 // context's stream).  See include/zkdl.h for the contract of every entry point.
 #include <string.h>
+#include <initializer_list>
 #include <mutex>
 #include <new>
+#include <utility>
 
 #include "zkdl_internal.h"
 
@@ -1424,12 +1426,60 @@ extern "C" int zkrelu_prove_at(zkdl_ctx* ctx, const int64_t* Z, const int64_t* G
                        npoints);
 }
 
+// ---- the list of claims a window leaves (host side, after the call has ended) ----
+struct ClaimList {
+    zkdl_claim* out;
+    size_t n;
+    const uint8_t* proof;   // the staged proof bytes of the call
+    void add(uint32_t tensor, std::initializer_list<std::pair<int, int>> segs, const uint8_t* value_le) {
+        zkdl_claim& c = out[n++];
+        memset(&c, 0, sizeof c);
+        c.tensor = tensor;
+        for (const auto& sg : segs) {
+            if (sg.second <= 0) continue;   // an axis of size one has no coordinates
+            c.seg_off[c.nseg] = (uint32_t)sg.first;
+            c.seg_len[c.nseg] = (uint32_t)sg.second;
+            c.nseg += 1;
+        }
+        memcpy(c.value.le, value_le, 32);
+    }
+    void add_at(uint32_t tensor, std::initializer_list<std::pair<int, int>> segs, size_t proof_off) {
+        add(tensor, segs, proof + proof_off);
+    }
+};
+
+// capacity of the caller's list, checked before anything runs
+static int claims_capacity(zkdl_claim* claims_out, size_t* nclaims, const zkdl_fr* points_out, size_t need) {
+    if (!claims_out) return ZKDL_OK;
+    if (!nclaims || !points_out) return ZKDL_EINVAL;
+    if (*nclaims < need) {
+        *nclaims = need;
+        return ZKDL_ESMALL;
+    }
+    return ZKDL_OK;
+}
+
+// byte offsets inside a product-sumcheck block that starts at `at`
+static size_t sc_claim0(size_t at) { return at + 16; }
+static size_t sc_final(size_t at, int rounds, int degree, int k) {
+    return at + 16 + 32 + (size_t)rounds * (degree + 1) * 32 + 32 * (size_t)k;
+}
+
+static Fr fr_from_le32(const uint8_t* p) {
+    Fr x;
+    memcpy(x.v, p, 32);
+    return fr_to_mont(x);
+}
+
 extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr,
-                               uint8_t* proof, size_t* proof_len, zkdl_fr* points_out, size_t* npoints) {
+                               uint8_t* proof, size_t* proof_len, zkdl_fr* points_out, size_t* npoints,
+                               zkdl_claim* claims_out, size_t* nclaims) {
     if (!ctx || !w || !tr || !w->A || !w->W || !w->GZ || !w->Zr || !w->GA) return ZKDL_EINVAL;
     if (!is_pow2(w->L) || !is_pow2(w->B) || !is_pow2(w->width) || !is_pow2(w->T)) return ZKDL_EINVAL;
     const uint64_t N = (uint64_t)w->L * w->T;
-    int rc = call_begin(ctx, tr);
+    int rc = claims_capacity(claims_out, nclaims, points_out, ZKDL_AGGREGATE_NCLAIMS);
+    if (rc != ZKDL_OK) return rc;
+    rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
     uint32_t hw[6] = {w->L, w->B, w->width, w->T, w->Q, w->R};
     zk_absorb_words(ctx, "aggregate", hw, 6);
@@ -1440,13 +1490,56 @@ extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_t
     zkdl_tensor tG = {TK_I32, 3, {sa[0], sa[1], sa[2], 1}, N * w->B * w->width, (void*)w->GZ, false};
     zkdl_tensor tW = {TK_I32, 3, {sw[0], sw[1], sw[2], 1}, N * w->width * w->width, (void*)w->W, false};
     // forward: Z = A W
+    const int cf = ctx->n_chal;
+    const size_t pf = ctx->proof_len;
     rc = enqueue_matmul(ctx, &tA, &tW, 0, 0, 0, 8, nullptr);
     // gradA: G_A^(l) = G_Z^(l+1) W^(l+1)T, slot of the last layer zero
+    const int ca = ctx->n_chal;
+    const size_t pa = ctx->proof_len;
     if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tG, &tW, 0, 1, w->L, 12, nullptr);
     // gradW: G_W^(l) = A^(l-1)T G_Z^(l)
+    const int cw = ctx->n_chal;
+    const size_t pw = ctx->proof_len;
     if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tA, &tG, 1, 0, 0, 16, nullptr);
+    const int cz = ctx->n_chal;
+    const size_t pz = ctx->proof_len;
     if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, w->Zr, w->GA, N * w->B * w->width, (int)w->Q, (int)w->R, 0, nullptr);
+    const size_t pend = ctx->proof_len;
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims_out) {
+        const int ln = ilog2_u64(N), lb = ilog2_u64(w->B), lw = ilog2_u64(w->width);
+        const int li = ln + lb + lw;
+        int lj = 0;
+        while ((1u << lj) < w->Q + w->R) ++lj;
+        ClaimList cl = {claims_out, 0, staged_proof(ctx)};
+        // a family's challenges: w (ln), u0 (l1), u1 (l3), then the rounds v_n (ln), v_i (l2)
+        {   // forward: l1 = lb, l2 = lw, l3 = lw
+            const int u0 = cf + ln, u1 = u0 + lb, vn = u1 + lw, vi = vn + ln, rounds = ln + lw;
+            cl.add_at(ZKDL_T_Z, {{cf, li}}, sc_claim0(pf));
+            cl.add_at(ZKDL_T_A, {{vn, ln}, {u0, lb}, {vi, lw}}, sc_final(pf, rounds, 3, 1));
+            cl.add_at(ZKDL_T_W, {{vn, ln}, {vi, lw}, {u1, lw}}, sc_final(pf, rounds, 3, 2));
+        }
+        {   // gradA: the same shape; its second operand is the transposed next layer's W
+            const int u0 = ca + ln, u1 = u0 + lb, vn = u1 + lw, vi = vn + ln, rounds = ln + lw;
+            cl.add_at(ZKDL_T_GA, {{ca, li}}, sc_claim0(pa));
+            cl.add_at(ZKDL_T_GZ_NEXT, {{vn, ln}, {u0, lb}, {vi, lw}}, sc_final(pa, rounds, 3, 1));
+            cl.add_at(ZKDL_T_W_NEXT, {{vn, ln}, {u1, lw}, {vi, lw}}, sc_final(pa, rounds, 3, 2));
+        }
+        {   // gradW: l1 = lw, l2 = lb, l3 = lw; its first operand is A transposed
+            const int u0 = cw + ln, u1 = u0 + lw, vn = u1 + lw, vi = vn + ln, rounds = ln + lb;
+            cl.add_at(ZKDL_T_GW, {{cw, ln + lw + lw}}, sc_claim0(pw));
+            cl.add_at(ZKDL_T_A, {{vn, ln}, {vi, lb}, {u0, lw}}, sc_final(pw, rounds, 3, 1));
+            cl.add_at(ZKDL_T_GZ, {{vn, ln}, {vi, lb}, {u1, lw}}, sc_final(pw, rounds, 3, 2));
+        }
+        // zkReLU: u_Z, u_A, u_GA, u_GZ (li each), u_bin (li + lj), r, r', rounds (li + lj), rho (3), merge (1 + lj)
+        const int c_v = cz + 5 * li + lj + 2, c_vm = c_v + li + lj + 3;
+        cl.add_at(ZKDL_T_ZR, {{cz, li}}, pz + 32);
+        cl.add_at(ZKDL_T_A_RELU, {{cz + li, li}}, pz + 64);
+        cl.add_at(ZKDL_T_GA, {{cz + 2 * li, li}}, pz + 96);
+        cl.add_at(ZKDL_T_GZ_RELU, {{cz + 3 * li, li}}, pz + 128);
+        cl.add_at(ZKDL_T_AUX, {{c_vm, 1}, {c_v, li}, {c_vm + 1, lj}}, pend - 64);
+        *nclaims = cl.n;
+    }
     return rc != ZKDL_OK ? rc : rc2;
 }
 
@@ -1542,14 +1635,17 @@ static int enqueue_reindex_linked(zkdl_ctx* ctx, const int32_t* X, uint64_t N, u
 }
 
 extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr,
-                                      uint8_t* proof, size_t* proof_len, zkdl_fr* points_out, size_t* npoints) {
+                                      uint8_t* proof, size_t* proof_len, zkdl_fr* points_out, size_t* npoints,
+                                      zkdl_claim* claims_out, size_t* nclaims) {
     if (!ctx || !w || !tr || !w->A || !w->W || !w->GZ || !w->Zr || !w->GA) return ZKDL_EINVAL;
     if (!is_pow2(w->L) || !is_pow2(w->B) || !is_pow2(w->width) || !is_pow2(w->T)) return ZKDL_EINVAL;
     const uint64_t N = (uint64_t)w->L * w->T;
     const int ln = ilog2_u64(N), lb = ilog2_u64(w->B), lw = ilog2_u64(w->width);
     const int li = ln + lb + lw;
     if (4 * li > ZK_CHAL_SET_MAX || N > ((uint64_t)1 << 28)) return ZKDL_EINVAL;
-    int rc = call_begin(ctx, tr);
+    int rc = claims_capacity(claims_out, nclaims, points_out, ZKDL_AGGREGATE_LINKED_NCLAIMS);
+    if (rc != ZKDL_OK) return rc;
+    rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
     // the index maps of the three re-indexings: the stack itself, and the stack whose slot (t, l)
     // is slot (t, l+1), zero for the last layer
@@ -1566,11 +1662,15 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
     zkdl_tensor tW = {TK_I32, 3, {sw[0], sw[1], sw[2], 1}, N * w->width * w->width, (void*)w->W, false};
     // challenges of a family: w (ln), u0 (l1), u1 (l3), then the rounds v_n (ln), v_i (l2)
     const int cf = ctx->n_chal;                       // forward: l1 = lb, l2 = lw, l3 = lw
+    const size_t pf = ctx->proof_len;
     if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tA, &tW, 0, 0, 0, 8, nullptr);
     const int ca = ctx->n_chal;                       // gradA: the same shape
     if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tG, &tW, 0, 1, w->L, 12, nullptr);
     const int cw = ctx->n_chal;                       // gradW: l1 = lw, l2 = lb, l3 = lw
+    const size_t pw = ctx->proof_len;
     if (rc == ZKDL_OK) rc = enqueue_matmul(ctx, &tA, &tG, 1, 0, 0, 16, nullptr);
+    int cz = 0, ri_g_v = 0, c_ma_end = 0, c_mw_end = 0;   // challenge indices the list of claims refers to
+    size_t pz = 0, pz_end = 0, p_rg_end = 0, p_ma_end = 0, p_mw_end = 0;
     const int f_u0 = cf + ln, f_vn = cf + ln + lb + lw, f_vi = f_vn + ln;
     const int a_u0 = ca + ln, a_u1 = a_u0 + lb, a_vn = ca + ln + lb + lw, a_vi = a_vn + ln;
     const int w_u0 = cw + ln, w_u1 = cw + ln + lw, w_vn = cw + ln + lw + lw, w_vi = w_vn + ln;
@@ -1593,7 +1693,10 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
         if (ctx->n_chal + 4 * li > ZK_MAX_CHAL) rc = ZKDL_EINVAL;
         if (rc == ZKDL_OK) {
             zk_launch_chal_set(ctx, ctx->n_chal, 4 * li, nullptr, &idx);
+            cz = ctx->n_chal;
+            pz = ctx->proof_len;
             rc = enqueue_zkrelu(ctx, w->Zr, w->GA, N * w->B * w->width, (int)w->Q, (int)w->R, 2, nullptr);
+            pz_end = ctx->proof_len;
         }
     }
     if (rc == ZKDL_OK) {
@@ -1612,7 +1715,9 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
             ChalIdx u = {};
             for (int i = 0; i < lb; ++i) u.v[i] = (int16_t)(a_u0 + i);
             for (int i = 0; i < lw; ++i) u.v[lb + i] = (int16_t)(a_vi + i);
+            ri_g_v = ctx->n_chal + 1;   // one coefficient, then the ln rounds
             rc = enqueue_reindex_linked(ctx, w->GZ, N, w->B, w->width, maps_down, pts, u, keep);
+            p_rg_end = ctx->proof_len;
         }
         // W: gradA's second final is an evaluation of the shifted, transposed stack: rows take u1
         if (rc == ZKDL_OK) {
@@ -1659,6 +1764,8 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
         at = 0;
         put(p1, w_vn, ln), put(p1, w_vi, lb), put(p1, w_u0, lw);
         rc = merge2(w->A, w->B, w->width, p0, p1);
+        c_ma_end = ctx->n_chal;
+        p_ma_end = ctx->proof_len;
         if (rc == ZKDL_OK) {
             ChalIdx q0 = {}, q1 = {};
             at = 0;
@@ -1666,9 +1773,47 @@ extern "C" int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w,
             at = 0;
             put(q1, ri_w_v, ln), put(q1, a_u1, lw), put(q1, a_vi, lw);
             rc = merge2(w->W, w->width, w->width, q0, q1);
+            c_mw_end = ctx->n_chal;
+            p_mw_end = ctx->proof_len;
         }
     }
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims_out) {
+        const uint8_t* sp = staged_proof(ctx);
+        const uint8_t* chal_le = ((const DevState*)ctx->host_stage)->chal_le;
+        ClaimList cl = {claims_out, 0, sp};
+        int lj = 0;
+        while ((1u << lj) < w->Q + w->R) ++lj;
+        const int lt = ilog2_u64(w->T), ll = ln - lt;
+        // a merge on a stack draws 2 coefficients, runs 1 + ld inner rounds (rho, v) and ln outer rounds (v_n);
+        // its last final is the claim left on the stack at (v_n, v)
+        const int ld_a = lb + lw, ld_w = lw + lw;
+        cl.add_at(ZKDL_T_A, {{c_ma_end - ln, ln}, {c_ma_end - ln - ld_a, ld_a}}, p_ma_end - 32);
+        cl.add_at(ZKDL_T_W, {{c_mw_end - ln, ln}, {c_mw_end - ln - ld_w, ld_w}}, p_mw_end - 32);
+        // G_Z: the re-indexing's final at (its rounds, gradA's u0, gradA's v_i)
+        cl.add_at(ZKDL_T_GZ, {{ri_g_v, ln}, {a_u0, lb}, {a_vi, lw}}, p_rg_end - 32);
+        // the last layer's share of forward's claim_0 and of gradW's final on G_Z, divided by beta~ of the
+        // layer coordinates (the low ll ones of the stack point) at L - 1, whose bits are all ones
+        auto last_layer = [&](size_t total_off, size_t part_off, int stack_chal) {
+            Fr fac = fr_one();
+            for (int c = lt; c < ln; ++c) fac = fr_mul(fac, fr_from_le32(chal_le + 32 * (size_t)(stack_chal + c)));
+            Fr diff = fr_sub(fr_from_le32(sp + total_off), fr_from_le32(sp + part_off));
+            Fr zero = fr_zero();
+            Fr val = fr_eq(fac, zero) ? zero : fr_mul(diff, host_inverse(fac));
+            return fr_from_mont(val);
+        };
+        (void)ll;
+        const int rounds_w = ln + lb;
+        Fr zl = last_layer(sc_claim0(pf), pz + 32, cf);
+        Fr gl = last_layer(sc_final(pw, rounds_w, 3, 2), pz + 128, w_vn);
+        cl.add(ZKDL_T_Z_LAST, {{cf, lt}, {f_u0, lb + lw}}, (const uint8_t*)zl.v);
+        cl.add(ZKDL_T_GZ_LAST, {{w_vn, lt}, {w_vi, lb}, {w_u1, lw}}, (const uint8_t*)gl.v);
+        cl.add_at(ZKDL_T_GW, {{cw, ln + lw + lw}}, sc_claim0(pw));
+        // zkReLU with given points: the 4 li given coordinates, u_bin (li + lj), r, r', rounds, rho, merge rounds
+        const int c_v = cz + 5 * li + lj + 2, c_vm = c_v + li + lj + 3;
+        cl.add_at(ZKDL_T_AUX, {{c_vm, 1}, {c_v, li}, {c_vm + 1, lj}}, pz_end - 64);
+        *nclaims = cl.n;
+    }
     for (void* p : keep) zk_free(ctx, p);
     free_reindex_linked(ctx, maps_a);
     free_reindex_linked(ctx, maps_down);

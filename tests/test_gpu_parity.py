@@ -656,6 +656,46 @@ def to_cuda_witness(wit):
     return out
 
 
+def expected_claims_unlinked(res, ln):
+    """The list aggregate_prove reports, from what the oracle's verifier returns: per matmul family the
+    claim on the product and the two finals, then zkReLU's four input claims and the claim on aux."""
+    out = []
+    names = {"fwd": ("Z", "A", "W"), "gradA": ("GA", "GZ_NEXT", "W_NEXT"), "gradW": ("GW", "A", "GZ")}
+    for fam in ("fwd", "gradA", "gradW"):
+        proof, pt = res[fam]
+        vn, vi = pt["v"][:ln], pt["v"][ln:]
+        y, x0, x1 = names[fam]
+        out.append(dict(tensor=y, point=pt["w"] + pt["u0"] + pt["u1"], value=proof.claim0))
+        if fam == "gradW":      # X0 = A transposed: in A's own (batch, feature) order the point is (v_n, v_i, u0)
+            out.append(dict(tensor=x0, point=vn + vi + pt["u0"], value=proof.finals[1]))
+        else:
+            out.append(dict(tensor=x0, point=vn + pt["u0"] + vi, value=proof.finals[1]))
+        if fam == "gradA":      # X1 = W of the next layer transposed: in W's (in, out) order (v_n, u1, v_i)
+            out.append(dict(tensor=x1, point=vn + pt["u1"] + vi, value=proof.finals[2]))
+        else:
+            out.append(dict(tensor=x1, point=vn + vi + pt["u1"], value=proof.finals[2]))
+    zk = res["zkrelu"]
+    for nm, key, c in zip(("ZR", "A_RELU", "GA", "GZ_RELU"), ("u_z", "u_a", "u_ga", "u_gz"), zk["c_in"]):
+        out.append(dict(tensor=nm, point=zk["points"][key], value=c))
+    out.append(dict(tensor="AUX", point=zk["aux_claim"]["point"], value=zk["aux_claim"]["value"]))
+    return out
+
+
+def expected_claims_linked(left):
+    """The list aggregate_prove_linked reports, from aggregate_linked_verify's result."""
+    (pa, va), = left["A"]
+    (pw, vw), = left["W"]
+    (pg, vg), = left["GZ"]
+    out = [dict(tensor="A", point=pa, value=va), dict(tensor="W", point=pw, value=vw),
+           dict(tensor="GZ", point=pg, value=vg)]
+    for nm in ("Zlast", "GZlast"):
+        point, value = left[nm]
+        out.append(dict(tensor={"Zlast": "Z_LAST", "GZlast": "GZ_LAST"}[nm], point=point, value=value))
+    out.append(dict(tensor="GW", point=left["GW"][0], value=left["GW"][1]))
+    out.append(dict(tensor="AUX", point=left["aux"][0], value=left["aux"][1]))
+    return out
+
+
 @pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 32, 8, 1), (1, 16, 2, 1)])
 def test_aggregate(lib, ctx, layers, width, batch, steps):
     say(f"aggregate L={layers} w={width} B={batch} T={steps}")
@@ -667,7 +707,8 @@ def test_aggregate(lib, ctx, layers, width, batch, steps):
     assert got["points"] == ots.challenges
     assert got["proof"] == buf
     assert tr.digest() == ots.digest()
-    P.aggregate_verify(got["proof"], OracleTranscript(33))
+    res = P.aggregate_verify(got["proof"], OracleTranscript(33))
+    assert got["claims_left"] == expected_claims_unlinked(res, (layers * steps).bit_length() - 1)
 
 
 @pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 32, 8, 1), (1, 16, 2, 1), (2, 4, 2, 4),
@@ -688,7 +729,8 @@ def test_aggregate_linked(lib, ctx, layers, width, batch, steps):
     zk = infos["zkrelu"]
     given = zk["u_z"] + zk["u_a"] + zk["u_ga"] + zk["u_gz"]
     assert got["points"] == ots.challenges[:before] + given + ots.challenges[before:]
-    P.aggregate_linked_verify(got["proof"], OracleTranscript(34))
+    left = P.aggregate_linked_verify(got["proof"], OracleTranscript(34))
+    assert got["claims_left"] == expected_claims_linked(left)
 
 
 def test_config1_fc_layer_plus_relu(lib, ctx):
@@ -907,9 +949,10 @@ def test_large_aggregates_by_properties(lib, ctx, name, layers, width, batch, st
     tr = lib.Transcript(CONFIG_SEED + cfg)
     got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr)
     ots = OracleTranscript(CONFIG_SEED + cfg)
-    P.aggregate_verify(got["proof"], ots)
+    res = P.aggregate_verify(got["proof"], ots)
     assert tr.digest() == ots.digest()
     assert got["points"] == ots.challenges
+    assert got["claims_left"] == expected_claims_unlinked(res, (layers * steps).bit_length() - 1)
     ctx.trim()
     # the same window with the claims chained: every link holds, and the one claim left on each of
     # A, G_Z and W (the merge on W runs over the whole stack, 2^26 or 2^27 elements) is the MLE of
@@ -920,6 +963,7 @@ def test_large_aggregates_by_properties(lib, ctx, name, layers, width, batch, st
     ots = OracleTranscript(CONFIG_SEED + cfg + 1)
     left = P.aggregate_linked_verify(got["proof"], ots)
     assert tr.digest() == ots.digest()
+    assert got["claims_left"] == expected_claims_linked(left)
     ln, lb, lw = (layers * steps).bit_length() - 1, batch.bit_length() - 1, width.bit_length() - 1
     for nm in ("A", "GZ", "W"):
         rows_bits = lb if nm != "W" else lw
