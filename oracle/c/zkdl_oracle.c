@@ -1008,6 +1008,114 @@ static int matmul_core(const fe* x0, const fe* x1, uint64_t n, uint64_t d1, uint
     return rc;
 }
 
+/* ---- batched matrix product, optimized aggregated protocol (App. B, Protocol tensor-op-aggr-optimized) ----
+ * Stack rounds t = 0 .. log N - 1: the prover sends, at x = 0, 1, 2,
+ *   f_t(x) = sum_{n'} beta~(w_[t+1:], n') sum_i X0~(v_<t, x, n', u0, i) X1~(v_<t, x, n', i, u1),
+ * the round polynomial without its factor beta~(w_t, x); the verifier's check is
+ * (1 - w_t) f_t(0) + w_t f_t(1) = claim, the next claim f_t(v_t).  Then the sumcheck of the single
+ * product sum_i X0~(v, u0, i) X1~(v, i, u1) (K = 2, degree 2, claim_0 not absorbed again).
+ * Header "sumcheck_matmul_ft" (N, D1, D2, D3); one draw (w, u0, u1); "c" claim_0; per stack round "f"
+ * (three evaluations) and a draw.  Proof: "ZKSF", log N, log D2, 0, claim_0, log N x 3 evaluations, SC block. */
+static int matmul_ft_core(const fe* x0, const fe* x1, uint64_t n, uint64_t d1, uint64_t d2, uint64_t d3, zko_ts* ts,
+                          wbuf* wb, mm_info* info, const char* what) {
+    int ln = ilog2_u64(n), l1 = ilog2_u64(d1), l2 = ilog2_u64(d2), l3 = ilog2_u64(d3);
+    if (ln < 0 || l1 < 0 || l2 < 0 || l3 < 0 || ln > 32 || l1 > 32 || l3 > 32 || ln + l2 > 64) return ZKO_EARG;
+    uint32_t hdr[4] = {(uint32_t)n, (uint32_t)d1, (uint32_t)d2, (uint32_t)d3};
+    ts_absorb_u32(ts, "sumcheck_matmul_ft", hdr, 4);
+    fe pt[96];
+    int rc = ts_draw(ts, ln + l1 + l3, pt);
+    if (rc) return rc;
+    info->ln = ln; info->l1 = l1; info->l2 = l2; info->l3 = l3;
+    for (int k = 0; k < ln; ++k) info->w[k] = pt[k];
+    for (int k = 0; k < l1; ++k) info->u0[k] = pt[ln + k];
+    for (int k = 0; k < l3; ++k) info->u1[k] = pt[ln + l1 + k];
+    fe* t0 = (fe*)malloc(sizeof(fe) * n * d2);
+    fe* t1 = (fe*)malloc(sizeof(fe) * n * d2);
+    if (!t0 || !t1) return ZKO_ENOMEM;
+    rc = partial_eval_fe(x0, n, d1, d2, info->u0, t0);
+    if (!rc) rc = partial_eval_fe(x1, n * d2, d3, 1, info->u1, t1);
+    if (rc) return rc;
+    const int nthreads = max_threads();
+    fe* part = (fe*)malloc(sizeof(fe) * (size_t)nthreads * 4);
+    if (!part) return ZKO_ENOMEM;
+    /* claim_0 = sum_n beta~(w, n) sum_i T0[n, i] T1[n, i] = Y~(w, u0, u1) */
+    fe* bw = beta_table(info->w, ln);
+    if (!bw) return ZKO_ENOMEM;
+    fe claim = fe_zero();
+    for (uint64_t row = 0; row < n; ++row) {
+        fe dot = fe_zero();
+        for (uint64_t i = 0; i < d2; ++i) dot = fe_add(dot, fe_mul(t0[row * d2 + i], t1[row * d2 + i]));
+        claim = fe_add(claim, fe_mul(bw[row], dot));
+    }
+    free(bw);
+    info->claim0 = claim;
+    wb_u32(wb, 0x46534B5Au);
+    wb_u32(wb, (uint32_t)ln);
+    wb_u32(wb, (uint32_t)l2);
+    wb_u32(wb, 0);
+    wb_fe(wb, claim);
+    ts_absorb_fe(ts, "c", &claim, 1);
+    uint64_t rows = n;
+    for (int t = 0; t < ln; ++t) {
+        if (g_progress) g_progress(what, t, ln);
+        const uint64_t half = rows / 2;
+        fe* bs = beta_table(info->w + t + 1, ln - t - 1); /* beta~(w_[t+1:], n'), half entries */
+        if (!bs) return ZKO_ENOMEM;
+        for (int i = 0; i < nthreads * 4; ++i) part[i] = fe_zero();
+#pragma omp parallel
+        {
+            fe acc[3] = {fe_zero(), fe_zero(), fe_zero()};
+#pragma omp for schedule(static)
+            for (uint64_t row = 0; row < half; ++row) {
+                fe dot[3] = {fe_zero(), fe_zero(), fe_zero()};
+                for (uint64_t i = 0; i < d2; ++i) {
+                    fe a = t0[row * d2 + i], b = t1[row * d2 + i];
+                    const fe da = fe_sub(t0[(row + half) * d2 + i], a), db = fe_sub(t1[(row + half) * d2 + i], b);
+                    for (int x = 0; x < 3; ++x) { /* a = lo + x (hi - lo) */
+                        dot[x] = fe_add(dot[x], fe_mul(a, b));
+                        a = fe_add(a, da);
+                        b = fe_add(b, db);
+                    }
+                }
+                for (int x = 0; x < 3; ++x) acc[x] = fe_add(acc[x], fe_mul(bs[row], dot[x]));
+            }
+            for (int x = 0; x < 3; ++x) part[my_thread() * 4 + x] = acc[x];
+        }
+        free(bs);
+        fe f[3];
+        for (int x = 0; x < 3; ++x) {
+            f[x] = fe_zero();
+            for (int th = 0; th < nthreads; ++th) f[x] = fe_add(f[x], part[th * 4 + x]);
+        }
+        /* g_t(x) = beta~(w_t, x) f_t(x): g_t(0) + g_t(1) = (1 - w_t) f_t(0) + w_t f_t(1) = claim */
+        fe chk = fe_add(fe_mul(fe_sub(fe_one(), info->w[t]), f[0]), fe_mul(info->w[t], f[1]));
+        if (!fe_eq(chk, claim)) return ZKO_ECHECK;
+        for (int x = 0; x < 3; ++x) wb_fe(wb, f[x]);
+        ts_absorb_fe(ts, "f", f, 3);
+        fe v;
+        rc = ts_draw(ts, 1, &v);
+        if (rc) return rc;
+        info->v[t] = v;
+#pragma omp parallel for schedule(static)
+        for (uint64_t b = 0; b < half * d2; ++b) {
+            t0[b] = fe_add(t0[b], fe_mul(v, fe_sub(t0[b + half * d2], t0[b])));
+            t1[b] = fe_add(t1[b], fe_mul(v, fe_sub(t1[b + half * d2], t1[b])));
+        }
+        claim = lagrange_eval(f, 3, v);
+        rows = half;
+    }
+    free(part);
+    vtab T[2] = {{t0, 0, l2}, {t1, 0, l2}};
+    scterm term = product_term(2);
+    fe all[2], inner0;
+    rc = sc_prove(T, 2, &term, 1, 2, l2, ts, 0, 0, 2, wb, info->v + ln, all, &inner0, info->finals, what);
+    free(t0);
+    free(t1);
+    if (rc) return rc;
+    if (!fe_eq(inner0, claim)) return ZKO_ECHECK; /* the single-product sumcheck starts at f_{n-1}(v_{n-1}) */
+    return 0;
+}
+
 /* ---- batched Hadamard product (Eq. exm-hadamard-batched): Y~(p) = sum_b beta~(p, b) X0(b) X1(b) ---- */
 static int hadamard_core(const fe* x0, const fe* x1, int d, zko_ts* ts, wbuf* wb) {
     if (d < 0 || d > 40) return ZKO_EARG;
@@ -1507,24 +1615,27 @@ typedef struct {
 } zko_witness;
 
 /* the three matmul families: forward Z = A W; gradA G_A = G_Z^(l+1) W^(l+1)T; gradW G_W = A^T G_Z */
-static int aggregate_matmuls(const zko_witness* w, zko_ts* ts, wbuf* wb, mm_info mm[3], fe** a_out, fe** w_out, fe** gz_out) {
+static int aggregate_matmuls(const zko_witness* w, zko_ts* ts, wbuf* wb, mm_info mm[3], fe** a_out, fe** w_out, fe** gz_out,
+                             int ft) {
     const uint64_t n = (uint64_t)w->L * w->T, B = w->B, wd = w->width;
+    int (*const matmul)(const fe*, const fe*, uint64_t, uint64_t, uint64_t, uint64_t, zko_ts*, wbuf*, mm_info*,
+                        const char*) = ft ? matmul_ft_core : matmul_core;
     fe* a = stack_fe(w->A, n, B, wd, 0, 0);
     fe* ww = stack_fe(w->W, n, wd, wd, 0, 0);
     if (!a || !ww) return ZKO_ENOMEM;
-    int rc = matmul_core(a, ww, n, B, wd, wd, ts, wb, &mm[0], "forward");
+    int rc = matmul(a, ww, n, B, wd, wd, ts, wb, &mm[0], "forward");
     if (rc) return rc;
     fe* gz_next = stack_fe(w->GZ, n, B, wd, (int)w->L, 0);
     fe* wt_next = stack_fe(w->W, n, wd, wd, (int)w->L, 1);
     if (!gz_next || !wt_next) return ZKO_ENOMEM;
-    rc = matmul_core(gz_next, wt_next, n, B, wd, wd, ts, wb, &mm[1], "gradA");
+    rc = matmul(gz_next, wt_next, n, B, wd, wd, ts, wb, &mm[1], "gradA");
     free(gz_next);
     free(wt_next);
     if (rc) return rc;
     fe* a_t = stack_fe(w->A, n, B, wd, 0, 1);
     fe* gz = stack_fe(w->GZ, n, B, wd, 0, 0);
     if (!a_t || !gz) return ZKO_ENOMEM;
-    rc = matmul_core(a_t, gz, n, wd, B, wd, ts, wb, &mm[2], "gradW");
+    rc = matmul(a_t, gz, n, wd, B, wd, ts, wb, &mm[2], "gradW");
     free(a_t);
     if (a_out) *a_out = a; else free(a);
     if (w_out) *w_out = ww; else free(ww);
@@ -1551,7 +1662,24 @@ int zko_aggregate_prove(const zko_witness* w, zko_ts* ts, uint8_t* proof, uint64
     wbuf wb = {proof, (size_t)cap, 0};
     aggregate_header(w, ts, &wb, "aggregate", 0x47414B5Au);
     mm_info mm[3];
-    int rc = aggregate_matmuls(w, ts, &wb, mm, 0, 0, 0);
+    int rc = aggregate_matmuls(w, ts, &wb, mm, 0, 0, 0, 0);
+    if (rc) return rc;
+    zk_info zi;
+    const uint64_t D = (uint64_t)w->L * w->T * w->B * w->width;
+    rc = zkrelu_core(w->Zr, w->GA, D, (int)w->Q, (int)w->R, ts, 0, 1, &wb, &zi);
+    if (rc) return rc;
+    *proof_len = wb.len;
+    return wb.len <= wb.cap ? 0 : ZKO_ESMALL;
+}
+
+/* the same window with the matrix-product families in the optimized aggregated form (f_t for the stack rounds) */
+int zko_aggregate_ft_prove(const zko_witness* w, zko_ts* ts, uint8_t* proof, uint64_t cap, uint64_t* proof_len) {
+    init_mu();
+    if (!witness_ok(w) || !ts) return ZKO_EARG;
+    wbuf wb = {proof, (size_t)cap, 0};
+    aggregate_header(w, ts, &wb, "aggregate_ft", 0x46414B5Au);
+    mm_info mm[3];
+    int rc = aggregate_matmuls(w, ts, &wb, mm, 0, 0, 0, 1);
     if (rc) return rc;
     zk_info zi;
     const uint64_t D = (uint64_t)w->L * w->T * w->B * w->width;
@@ -1570,7 +1698,7 @@ int zko_aggregate_linked_prove(const zko_witness* w, zko_ts* ts, uint8_t* proof,
     aggregate_header(w, ts, &wb, "aggregate_linked", 0x4C414B5Au);
     mm_info mm[3];
     fe *a = 0, *ww = 0, *gz = 0;
-    int rc = aggregate_matmuls(w, ts, &wb, mm, &a, &ww, &gz);
+    int rc = aggregate_matmuls(w, ts, &wb, mm, &a, &ww, &gz, 0);
     if (rc) return rc;
     const uint64_t n = (uint64_t)w->L * w->T, B = w->B, wd = w->width;
     const int ln = ilog2_u64(n), lb = ilog2_u64(B), lw = ilog2_u64(wd);
@@ -1690,6 +1818,22 @@ int zko_matmul_prove(const uint8_t* x0, const uint8_t* x1, uint64_t n, uint64_t 
     wbuf wb = {proof, (size_t)cap, 0};
     mm_info info;
     int rc = matmul_core(a, b, n, d1, d2, d3, ts, &wb, &info, "matmul");
+    free(a);
+    free(b);
+    if (rc) return rc;
+    *proof_len = wb.len;
+    return wb.len <= wb.cap ? 0 : ZKO_ESMALL;
+}
+
+int zko_matmul_ft_prove(const uint8_t* x0, const uint8_t* x1, uint64_t n, uint64_t d1, uint64_t d2, uint64_t d3, zko_ts* ts,
+                        uint8_t* proof, uint64_t cap, uint64_t* proof_len) {
+    init_mu();
+    fe* a = load_table(x0, n * d1 * d2);
+    fe* b = load_table(x1, n * d2 * d3);
+    if (!a || !b) return ZKO_ENOMEM;
+    wbuf wb = {proof, (size_t)cap, 0};
+    mm_info info;
+    int rc = matmul_ft_core(a, b, n, d1, d2, d3, ts, &wb, &info, "matmul_ft");
     free(a);
     free(b);
     if (rc) return rc;

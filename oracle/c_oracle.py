@@ -201,6 +201,15 @@ def matmul_prove(x0_le, shape0, x1_le, shape1, ts):
                 C.c_uint64(d2), C.c_uint64(d3), C.c_void_p(ts._h))
 
 
+def matmul_ft_prove(x0_le, shape0, x1_le, shape1, ts):
+    """The same product with the messages of the optimized aggregated protocol (App. B)."""
+    n, d1, d2 = shape0
+    n_, d2_, d3 = shape1
+    assert n == n_ and d2 == d2_
+    return _run(load().zko_matmul_ft_prove, bytes(x0_le), bytes(x1_le), C.c_uint64(n), C.c_uint64(d1),
+                C.c_uint64(d2), C.c_uint64(d3), C.c_void_p(ts._h))
+
+
 def hadamard_prove(x0_le, x1_le, ts):
     n = len(x0_le) // 32
     d = n.bit_length() - 1
@@ -252,10 +261,12 @@ def _witness(wit):
     return w, keep
 
 
-def aggregate_prove(wit, ts, linked=False):
-    """wit as oracle.protocols.aggregate_prove takes it (integer stacks).  Returns the proof bytes."""
+def aggregate_prove(wit, ts, linked=False, ft=False):
+    """wit as oracle.protocols.aggregate_prove takes it (integer stacks).  Returns the proof bytes.
+    linked: aggregate_linked_prove; ft: aggregate_ft_prove."""
+    assert not (linked and ft)
     w, keep = _witness(wit)
-    fn = load().zko_aggregate_linked_prove if linked else load().zko_aggregate_prove
+    fn = load().zko_aggregate_linked_prove if linked else load().zko_aggregate_ft_prove if ft else load().zko_aggregate_prove
     out = _run(fn, C.byref(w), C.c_void_p(ts._h))
     del keep
     return out

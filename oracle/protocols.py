@@ -765,6 +765,68 @@ def aggregate_verify(buf, ts):
 
 
 # --------------------------------------------------------------------------
+# the same window with the matrix-product families in the optimized aggregated form (App. B,
+# Protocol tensor-op-aggr-optimized): f_t for the stack rounds, then one matrix product's sumcheck
+# --------------------------------------------------------------------------
+ZKAF_MAGIC = 0x46414B5A   # bytes "ZKAF"
+
+
+def aggregate_ft_prove(wit, ts):
+    """aggregate_prove with matmul_ft_prove for forward, gradA and gradW: per family the log N stack
+    rounds carry f_t (degree 2, no table for beta~(w, .)), then the single product's sumcheck
+    (K = 2).  zkReLU as before.  Header label "aggregate_ft", proof "ZKAF" + the same eight words."""
+    n_layers, bsz, width, steps = wit["L"], wit["B"], wit["width"], wit["T"]
+    q, r_bits = wit["Q"], wit["R"]
+    n = n_layers * steps
+    a = np.asarray(wit["A"]).reshape(n, bsz, width)
+    w = np.asarray(wit["W"]).reshape(n, width, width)
+    gz = np.asarray(wit["GZ"]).reshape(n, bsz, width)
+    ts.absorb_u32(b"aggregate_ft", [n_layers, bsz, width, steps, q, r_bits])
+    parts = [struct.pack("<IIIIIIII", ZKAF_MAGIC, n_layers, bsz, width, steps, q, r_bits, 0)]
+    infos = {}
+    buf, infos["fwd"] = matmul_ft_prove(fr_array(a), [n, bsz, width], fr_array(w), [n, width, width], ts)
+    parts.append(buf)
+    gz_next = shift_layers(gz, n_layers)
+    wt_next = np.transpose(shift_layers(w, n_layers), (0, 2, 1))
+    buf, infos["gradA"] = matmul_ft_prove(fr_array(gz_next), [n, bsz, width], fr_array(wt_next),
+                                          [n, width, width], ts)
+    parts.append(buf)
+    buf, infos["gradW"] = matmul_ft_prove(fr_array(np.transpose(a, (0, 2, 1))), [n, width, bsz], fr_array(gz),
+                                          [n, bsz, width], ts)
+    parts.append(buf)
+    buf, infos["zkrelu"] = zkrelu_prove(np.asarray(wit["Zr"]).reshape(-1).tolist(),
+                                        np.asarray(wit["GA"]).reshape(-1).tolist(), q, r_bits, ts)
+    parts.append(buf)
+    return b"".join(parts), infos
+
+
+def _ft_block_end(buf, off):
+    """End of the "ZKSF" block that starts at off."""
+    magic, ln, _, _ = struct.unpack_from("<IIII", buf, off)
+    assert magic == FT_MAGIC
+    _, end = SumcheckProof.from_bytes(buf, off + 16 + 32 + 96 * ln)
+    return end
+
+
+def aggregate_ft_verify(buf, ts):
+    """Per family (claim_0, finals (X0~, X1~), points), then zkReLU's result."""
+    magic, n_layers, bsz, width, steps, q, r_bits, _ = struct.unpack_from("<IIIIIIII", buf, 0)
+    assert magic == ZKAF_MAGIC
+    n = n_layers * steps
+    ts.absorb_u32(b"aggregate_ft", [n_layers, bsz, width, steps, q, r_bits])
+    off = 32
+    out = {}
+    for name, (d1, d2, d3) in (("fwd", (bsz, width, width)), ("gradA", (bsz, width, width)),
+                               ("gradW", (width, bsz, width))):
+        end = _ft_block_end(buf, off)
+        out[name] = matmul_ft_verify(buf[off:end], n, d1, d2, d3, ts)
+        off = end
+    off, out["zkrelu"] = zkrelu_verify(buf, ts, off)
+    assert off == len(buf)
+    return out
+
+
+# --------------------------------------------------------------------------
 # the same window with the claims linked (Sec. 3.2, Sec. 4 Eq. sc-reindex, Protocol zkdl)
 # --------------------------------------------------------------------------
 ZKAL_MAGIC = 0x4C414B5A   # "ZKAL"

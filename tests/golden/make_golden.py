@@ -104,6 +104,17 @@ def aggregate_linked_case():
             "digest_hex": ts.digest().hex()}
 
 
+def aggregate_ft_case():
+    """The same window with the matrix products in the optimized aggregated form (App. B)."""
+    wit = fcnn_window(2307162730 + 90, n_layers=2, width=4, batch=2, steps=2)
+    ts = Transcript(16)
+    buf, _ = P.aggregate_ft_prove(wit, ts)
+    return {"protocol": "aggregate_prove_ft", "cite": "App. B, Protocol tensor-op-aggr-optimized; Protocol zkdl",
+            "seed": 16, "workload": "fcnn_window(2307162730 + 90, n_layers=2, width=4, batch=2, steps=2)",
+            "proof_hex": bytes(buf).hex(), "challenges": [hex(v) for v in ts.challenges],
+            "digest_hex": ts.digest().hex()}
+
+
 def reindex_case():
     """Re-indexing sumcheck (Eq. sc-reindex): stack of N = 4 tensors of D = 8, two sub-stacks."""
     rng = np.random.default_rng(20230718)
@@ -149,6 +160,7 @@ if __name__ == "__main__":
                      ("zkrelu_d4_q5_r3", zkrelu_case), ("zkrelu_at_d4_q5_r3", zkrelu_at_case),
                      ("aggregate_l2_w4_b2_t2", aggregate_case),
                      ("aggregate_linked_l2_w4_b2_t2", aggregate_linked_case),
+                     ("aggregate_ft_l2_w4_b2_t2", aggregate_ft_case),
                      ("reindex_n4_d8_k2", reindex_case), ("merge_d4_k3", merge_case),
                      ("stack_merge_n4_d8_k2", stack_merge_case)):
         with open(os.path.join(HERE, name + ".json"), "w") as f:

@@ -45,6 +45,8 @@ def oracle_run(g):
         buf = P.stack_merge_prove(fr_array(np.array(g["x"])), g["x_shape"][0], g["x_shape"][1], pts, ts)[0]
     elif g["protocol"] == "aggregate_prove_linked":
         buf = P.aggregate_linked_prove(fcnn_window(2307162730 + 90, 2, 4, 2, 2), ts)[0]
+    elif g["protocol"] == "aggregate_prove_ft":
+        buf = P.aggregate_ft_prove(fcnn_window(2307162730 + 90, 2, 4, 2, 2), ts)[0]
     else:
         out = P.aggregate_prove(fcnn_window(2307162730 + 90, 2, 4, 2, 2), ts)
         buf = out[0] if isinstance(out, tuple) else out
@@ -63,7 +65,7 @@ def _without_repeats(points, drawn):
 
 
 NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "zkrelu_d4_q5_r3", "zkrelu_at_d4_q5_r3", "aggregate_l2_w4_b2_t2",
-         "aggregate_linked_l2_w4_b2_t2", "merge_d4_k3", "stack_merge_n4_d8_k2",
+         "aggregate_linked_l2_w4_b2_t2", "aggregate_ft_l2_w4_b2_t2", "merge_d4_k3", "stack_merge_n4_d8_k2",
          "reindex_n4_d8_k2"]
 
 
@@ -114,7 +116,8 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
         dw = {k: wit[k] for k in ("L", "B", "width", "T", "Q", "R")}
         for k in ("A", "W", "GZ", "Zr", "GA"):
             dw[k] = torch.from_numpy(np.ascontiguousarray(wit[k])).cuda()
-        got = lib.aggregate_prove(ctx, dw, tr, linked=g["protocol"] == "aggregate_prove_linked")
+        got = lib.aggregate_prove(ctx, dw, tr, linked=g["protocol"] == "aggregate_prove_linked",
+                                  ft=g["protocol"] == "aggregate_prove_ft")
     if g["protocol"] == "aggregate_prove_linked":
         # the four points given to zkReLU are not draws: they come back in front of its own
         drawn = {int(v, 16) for v in g["challenges"]}

@@ -101,6 +101,16 @@ def test_matmul_matches_python_tier(n, d1, d2, d3):
     _same(cts, ts, c_oracle.matmul_prove(x0, [n, d1, d2], x1, [n, d2, d3], cts), buf)
 
 
+@pytest.mark.parametrize("n,d1,d2,d3", [(1, 2, 4, 2), (4, 8, 16, 2), (2, 1, 2, 1), (8, 1, 1, 4), (1, 1, 1, 1), (16, 2, 8, 4)])
+def test_matmul_ft_matches_python_tier(n, d1, d2, d3):
+    rng = np.random.default_rng(11 * n + d2)
+    x0 = uniform_fr_limbs(rng, n * d1 * d2).tobytes()
+    x1 = uniform_fr_limbs(rng, n * d2 * d3).tobytes()
+    ts, cts = Transcript(3), c_oracle.Transcript(3)
+    buf, _ = P.matmul_ft_prove(fr_array_from_le(x0, n * d1 * d2), [n, d1, d2], fr_array_from_le(x1, n * d2 * d3), [n, d2, d3], ts)
+    _same(cts, ts, c_oracle.matmul_ft_prove(x0, [n, d1, d2], x1, [n, d2, d3], cts), buf)
+
+
 @pytest.mark.parametrize("d", [0, 1, 5, 9])
 def test_hadamard_matches_python_tier(d):
     rng = np.random.default_rng(60 + d)
@@ -177,15 +187,20 @@ def test_stack_merge_matches_python_tier(n, d, k, bind):
 
 
 @pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 16, 2, 1), (1, 16, 2, 1), (2, 4, 2, 4), (8, 8, 4, 1)])
-@pytest.mark.parametrize("linked", [False, True])
+@pytest.mark.parametrize("linked", [False, True, "ft"])
 def test_aggregate_matches_python_tier(layers, width, batch, steps, linked):
     from workloads import fcnn_window, CONFIG_SEED
     wit = fcnn_window(CONFIG_SEED + 50 + layers, layers, width, batch, steps)
     ts, cts = Transcript(14), c_oracle.Transcript(14)
     for t in (ts, cts):
         t.absorb(b"weights", b"\x07" * 32)       # a caller's binding of its tensors
-    buf, _ = (P.aggregate_linked_prove if linked else P.aggregate_prove)(wit, ts)
-    _same(cts, ts, c_oracle.aggregate_prove(wit, cts, linked=linked), buf)
+    if linked == "ft":
+        buf, _ = P.aggregate_ft_prove(wit, ts)
+        got = c_oracle.aggregate_prove(wit, cts, ft=True)
+    else:
+        buf, _ = (P.aggregate_linked_prove if linked else P.aggregate_prove)(wit, ts)
+        got = c_oracle.aggregate_prove(wit, cts, linked=linked)
+    _same(cts, ts, got, buf)
 
 
 @pytest.mark.parametrize("name", ["aggregate_l2_w4_b2_t2", "aggregate_linked_l2_w4_b2_t2", "zkrelu_d4_q5_r3", "matmul_n2_2x4x2"])

@@ -258,6 +258,43 @@ def test_aggregate_small_network():
             assert (gz_prev[k] == wit["GZ"][k]).all()
 
 
+@pytest.mark.parametrize("n_layers,width,batch,steps", [(2, 8, 4, 2), (4, 4, 2, 1), (1, 8, 2, 1)])
+def test_aggregate_ft_claims_are_evaluations_of_the_stacks(n_layers, width, batch, steps):
+    """The window with the optimized aggregated protocol for its matrix products: the verifier accepts,
+    each family's claim_0 is the MLE of the exact integer product, its finals are MLEs of the operand
+    stacks, the same tensor evaluations as the g_t form leaves at its own challenges, and a flipped
+    byte anywhere is refused."""
+    wit = fcnn_window(CONFIG_SEED + 120, n_layers=n_layers, width=width, batch=batch, steps=steps)
+    n = n_layers * steps
+    ln = n.bit_length() - 1
+    ts = Transcript(21)
+    buf, infos = P.aggregate_ft_prove(wit, ts)
+    tv = Transcript(21)
+    res = P.aggregate_ft_verify(buf, tv)
+    assert tv.digest() == ts.digest() and tv.challenges == ts.challenges
+    a, wt, gz = (wit[k].astype(object) for k in ("A", "W", "GZ"))
+    prods = {"fwd": np.einsum("nij,njk->nik", a, wt), "gradA": wit["GA"].astype(object),
+             "gradW": np.einsum("nji,njk->nik", a, gz)}
+    ops = {"fwd": (a, wt), "gradA": (P.shift_layers(wit["GZ"], n_layers).astype(object),
+                                     np.transpose(P.shift_layers(wit["W"], n_layers), (0, 2, 1)).astype(object)),
+           "gradW": (np.transpose(a, (0, 2, 1)), gz)}
+    for fam in ("fwd", "gradA", "gradW"):
+        claim0, finals, pt = res[fam]
+        vn, vi = pt["v"][:ln], pt["v"][ln:]
+        assert claim0 == mle_eval(fr_array(prods[fam]), pt["w"] + pt["u0"] + pt["u1"]), fam
+        assert finals[0] == mle_eval(fr_array(ops[fam][0]), vn + pt["u0"] + vi), fam
+        assert finals[1] == mle_eval(fr_array(ops[fam][1]), vn + vi + pt["u1"]), fam
+    # shorter than the g_t form: per round one evaluation less, one final less, one more block header and claim
+    buf_g, _ = P.aggregate_prove(wit, Transcript(21))
+    lw, lb = width.bit_length() - 1, batch.bit_length() - 1
+    assert len(buf_g) - len(buf) == 3 * (32 * ln - 16) + 32 * (2 * lw + lb)
+    for pos in (40, len(buf) // 3, len(buf) // 2, len(buf) - 5):
+        bad = bytearray(buf)
+        bad[pos] ^= 1
+        with pytest.raises(AssertionError):
+            P.aggregate_ft_verify(bytes(bad), Transcript(21))
+
+
 @pytest.mark.parametrize("n_layers,width,batch,steps", [(2, 8, 4, 2), (4, 4, 2, 1), (2, 4, 2, 4)])
 def test_aggregate_linked_claims_are_evaluations_of_the_stacks(n_layers, width, batch, steps):
     """Every claim the linked proof leaves is the MLE of the tensor it names at the point it
