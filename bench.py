@@ -270,6 +270,8 @@ def main():
         out["config"]["proof_ms_batch64_8layer_step_min"] = 1e3 * ag_min
         lk_med, _ = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + 3), linked=True), 5)
         out["config"]["proof_ms_batch64_8layer_step_linked"] = 1e3 * lk_med
+        ft_med, _ = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + 3), ft=True), 5)
+        out["config"]["proof_ms_batch64_8layer_step_ft"] = 1e3 * ft_med
         out["config"]["paper_context"] = ("paper: < 1 s per batch-64 update, 8-layer 10M-parameter net, one "
                                           "Tesla A100, whole protocol including commitments (not comparable)")
         del dw
@@ -286,6 +288,8 @@ def main():
                 out["config"]["proof_ms_" + key + "_per_step"] = 1e3 * med / st
             med, _ = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + cfg), linked=True), 3)
             out["config"]["proof_ms_" + key + "_linked"] = 1e3 * med
+            med, _ = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + cfg), ft=True), 3)
+            out["config"]["proof_ms_" + key + "_ft"] = 1e3 * med
             del dw, wit
             ctx.trim()
     if not args.no_cpu_baseline:

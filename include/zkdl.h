@@ -362,6 +362,15 @@ int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* 
                     size_t* proof_len, zkdl_fr* points_out, size_t* npoints, zkdl_claim* claims_out,
                     size_t* nclaims);
 
+/* aggregate_prove_ft: aggregate_prove with the three matrix-product families in the optimized aggregated
+ * form of App. B (Protocol tensor-op-aggr-optimized), each as in sumcheck_matmul_ft: the log2 N stack
+ * rounds send f_t(0), f_t(1), f_t(2) and fold two tables (no table for beta~(w, .)), then the single
+ * product's sumcheck follows; zkReLU as in aggregate_prove.  Transcript header "aggregate_ft" (L, B, width,
+ * T', Q, R).  Proof: "ZKAF", L, B, width, T', Q, R, 0, three "ZKSF" blocks (forward, gradA, gradW), the
+ * zkReLU proof. */
+int aggregate_prove_ft(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
+                       size_t* proof_len, zkdl_fr* points_out, size_t* npoints);
+
 /* aggregate_prove_linked: the same four families with their claims chained (Sec. 3.2: the
  * claims zkReLU starts from are left by the other operations' sumchecks; Sec. 4, Eq.
  * sc-reindex: claims on stacks whose slots are shifted become claims on the stack itself;

@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = [
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
     "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_hadamard",
-    "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
+    "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "aggregate_prove_ft", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read", "zkdl_selfbench",
 ]
 
@@ -89,6 +89,7 @@ def load_library():
         "zkrelu_prove_at": [vp, vp, vp, u64, i, i, i, vp, vp, vp, psz, vp, vp, psz],
         "aggregate_prove": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz, vp, psz],
         "aggregate_prove_linked": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz, vp, psz],
+        "aggregate_prove_ft": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
         "zkdl_host_fr_mul": [vp, vp, vp], "zkdl_selfcheck_constants": [],
         "zkdl_ctx_profile_enable": [vp, i], "zkdl_ctx_profile_reset": [vp],
         "zkdl_ctx_profile_read": [vp, i, C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
@@ -409,9 +410,10 @@ def zkrelu_prove(ctx, z, ga, tr, q=32, r=16, points=None):
     return o.result()
 
 
-def aggregate_prove(ctx, wit, tr, linked=False):
+def aggregate_prove(ctx, wit, tr, linked=False, ft=False):
     """wit: dict with L, B, width, T, Q, R and CUDA tensors A, W, GZ (int32), Zr, GA (int64).
-    linked: the claims of the four families chained (aggregate_prove_linked)."""
+    linked: the claims of the four families chained (aggregate_prove_linked); ft: the matrix-product
+    families in the optimized aggregated form (aggregate_prove_ft)."""
     import torch
     for k, dt in (("A", torch.int32), ("W", torch.int32), ("GZ", torch.int32), ("Zr", torch.int64),
                   ("GA", torch.int64)):
@@ -423,6 +425,11 @@ def aggregate_prove(ctx, wit, tr, linked=False):
                     wit["A"].data_ptr(), wit["W"].data_ptr(), wit["GZ"].data_ptr(), wit["Zr"].data_ptr(),
                     wit["GA"].data_ptr())
     o = _Outputs(0)
+    if ft:
+        assert not linked
+        _check(load_library().aggregate_prove_ft(ctx.handle, C.byref(w), tr.handle, o.proof, C.byref(o.proof_len),
+                                                 o.points, C.byref(o.npoints)), "aggregate_prove_ft", ctx)
+        return o.result()
     name = "aggregate_prove_linked" if linked else "aggregate_prove"
     claims = (Claim * 16)()
     nclaims = C.c_size_t(16)

@@ -822,7 +822,7 @@ extern "C" int sumcheck_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_
 // Enqueues the optimized aggregated protocol for Y[n] = op(X0[n]) op(X1[n]) (App. B).  Final
 // claims are left in scal[scal_base .. +2): X0~, X1~.
 static int enqueue_matmul_ft(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1, int tr0, int tr1,
-                             int scal_base) {
+                             uint32_t shift, int scal_base) {
     if (X0->ndim != 3 || X1->ndim != 3 || X0->shape[0] != X1->shape[0]) return ZKDL_EINVAL;
     const uint64_t N = X0->shape[0];
     const uint64_t D1 = tr0 ? X0->shape[2] : X0->shape[1];
@@ -842,7 +842,7 @@ static int enqueue_matmul_ft(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_te
     const uint64_t len = N * D2;
     // scratch: suffix tables of w (sizes N/2, N/4, .., 1), beta tables (D1, D3), two source tables,
     // the work tables
-    void* mem = zk_alloc(ctx, (N + D1 + D3 + 2 * len) * 32 + zk_sumcheck_work_bytes(2, ln + l2));
+    void* mem = zk_alloc(ctx, (N + D1 + D3 + 3 * len) * 32 + zk_sumcheck_work_bytes(2, ln + l2));
     if (!mem) return ZKDL_ENOMEM;
     uint32_t* base = (uint32_t*)mem;
     FrTab wsuf[16];
@@ -866,19 +866,25 @@ static int enqueue_matmul_ft(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_te
         src[k] = make_tab(base, len);
         base += 8 * len;
     }
+    FrTab tmp = make_tab(base, len);   // shift != 0: slot n of both tables takes slot n+1 (zero in each period's last)
+    base += 8 * len;
     void* work = base;
     int rc = zk_build_beta_many(ctx, jobs, nj);
     if (rc == ZKDL_OK) {
         FrTab s0 = make_tab(X0->data, X0->numel);
         const void* sp = X0->kind == TK_FR ? (const void*)&s0 : X0->data;
-        if (!tr0) rc = zk_partial_eval(ctx, X0->kind, sp, N, D1, D2, bu0, src[0]);
-        else rc = zk_partial_eval(ctx, X0->kind, sp, N * D2, D1, 1, bu0, src[0]);
+        FrTab dst = shift ? tmp : src[0];
+        if (!tr0) rc = zk_partial_eval(ctx, X0->kind, sp, N, D1, D2, bu0, dst);
+        else rc = zk_partial_eval(ctx, X0->kind, sp, N * D2, D1, 1, bu0, dst);
+        if (rc == ZKDL_OK && shift) zk_launch_shift_rows(ctx, tmp, N, D2, shift, src[0]);
     }
     if (rc == ZKDL_OK) {
         FrTab s1 = make_tab(X1->data, X1->numel);
         const void* sp = X1->kind == TK_FR ? (const void*)&s1 : X1->data;
-        if (!tr1) rc = zk_partial_eval(ctx, X1->kind, sp, N * D2, D3, 1, bu1, src[1]);
-        else rc = zk_partial_eval(ctx, X1->kind, sp, N, D3, D2, bu1, src[1]);
+        FrTab dst = shift ? tmp : src[1];
+        if (!tr1) rc = zk_partial_eval(ctx, X1->kind, sp, N * D2, D3, 1, bu1, dst);
+        else rc = zk_partial_eval(ctx, X1->kind, sp, N, D3, D2, bu1, dst);
+        if (rc == ZKDL_OK && shift) zk_launch_shift_rows(ctx, tmp, N, D2, shift, src[1]);
     }
     if (rc == ZKDL_OK) rc = zk_matmul_ft(ctx, src, work, ln, l2, wsuf, cw, scal_base);
     zk_free(ctx, mem);
@@ -892,7 +898,7 @@ extern "C" int sumcheck_matmul_ft(zkdl_ctx* ctx, const zkdl_tensor* X0, const zk
     if (X0->ndim != 3 || X1->ndim != 3) return ZKDL_EINVAL;
     int rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
-    rc = enqueue_matmul_ft(ctx, X0, X1, transpose_x0 != 0, transpose_x1 != 0, 0);
+    rc = enqueue_matmul_ft(ctx, X0, X1, transpose_x0 != 0, transpose_x1 != 0, 0, 0);
     zkdl_fr tmp[2];
     int ids[2] = {0, 1};
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 2, tmp);
@@ -1540,6 +1546,33 @@ extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_t
         cl.add_at(ZKDL_T_AUX, {{c_vm, 1}, {c_v, li}, {c_vm + 1, lj}}, pend - 64);
         *nclaims = cl.n;
     }
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
+// The same window with its three matrix-product families in the optimized aggregated form (App. B,
+// Protocol tensor-op-aggr-optimized): the stack rounds carry f_t and fold two tables, not three.
+static const uint32_t ZKAF_MAGIC = 0x46414B5Au;
+
+extern "C" int aggregate_prove_ft(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
+                                  size_t* proof_len, zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !w || !tr || !w->A || !w->W || !w->GZ || !w->Zr || !w->GA) return ZKDL_EINVAL;
+    if (!is_pow2(w->L) || !is_pow2(w->B) || !is_pow2(w->width) || !is_pow2(w->T)) return ZKDL_EINVAL;
+    const uint64_t N = (uint64_t)w->L * w->T;
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    uint32_t hw[6] = {w->L, w->B, w->width, w->T, w->Q, w->R};
+    zk_absorb_words(ctx, "aggregate_ft", hw, 6);
+    uint32_t hdr[8] = {ZKAF_MAGIC, w->L, w->B, w->width, w->T, w->Q, w->R, 0};
+    zk_write_proof_words(ctx, hdr, 8);
+    uint64_t sa[3] = {N, w->B, w->width}, sw[3] = {N, w->width, w->width};
+    zkdl_tensor tA = {TK_I32, 3, {sa[0], sa[1], sa[2], 1}, N * w->B * w->width, (void*)w->A, false};
+    zkdl_tensor tG = {TK_I32, 3, {sa[0], sa[1], sa[2], 1}, N * w->B * w->width, (void*)w->GZ, false};
+    zkdl_tensor tW = {TK_I32, 3, {sw[0], sw[1], sw[2], 1}, N * w->width * w->width, (void*)w->W, false};
+    rc = enqueue_matmul_ft(ctx, &tA, &tW, 0, 0, 0, 8);
+    if (rc == ZKDL_OK) rc = enqueue_matmul_ft(ctx, &tG, &tW, 0, 1, w->L, 12);
+    if (rc == ZKDL_OK) rc = enqueue_matmul_ft(ctx, &tA, &tG, 1, 0, 0, 16);
+    if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, w->Zr, w->GA, N * w->B * w->width, (int)w->Q, (int)w->R, 0, nullptr);
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
     return rc != ZKDL_OK ? rc : rc2;
 }
 

@@ -711,6 +711,21 @@ def test_aggregate(lib, ctx, layers, width, batch, steps):
     assert got["claims_left"] == expected_claims_unlinked(res, (layers * steps).bit_length() - 1)
 
 
+@pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 32, 8, 1), (1, 16, 2, 1), (2, 4, 2, 4), (8, 16, 4, 16)])
+def test_aggregate_ft(lib, ctx, layers, width, batch, steps):
+    """The window with its matrix products in the optimized aggregated form (f_t for the stack rounds)."""
+    say(f"aggregate ft L={layers} w={width} B={batch} T={steps}")
+    wit = fcnn_window(CONFIG_SEED + 70 + layers, layers, width, batch, steps)
+    tr = lib.Transcript(35)
+    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr, ft=True)
+    ots = OracleTranscript(35)
+    buf, _ = P.aggregate_ft_prove(wit, ots)
+    assert got["points"] == ots.challenges
+    assert got["proof"] == buf
+    assert tr.digest() == ots.digest()
+    P.aggregate_ft_verify(got["proof"], OracleTranscript(35))
+
+
 @pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 32, 8, 1), (1, 16, 2, 1), (2, 4, 2, 4),
                                                       (4, 16, 8, 4)])
 def test_aggregate_linked(lib, ctx, layers, width, batch, steps):

@@ -33,7 +33,7 @@ def to_cuda_witness(wit):
     return out
 
 
-def _oracle_prove(wit, seed, linked, capsys, name):
+def _oracle_prove(wit, seed, linked, capsys, name, ft=False):
     """The C tier's proof, with a progress line per sumcheck round on the real stdout."""
     t0 = time.time()
 
@@ -45,17 +45,17 @@ def _oracle_prove(wit, seed, linked, capsys, name):
     with capsys.disabled():
         c_oracle.set_progress(progress)
         try:
-            buf = c_oracle.aggregate_prove(wit, cts, linked=linked)
+            buf = c_oracle.aggregate_prove(wit, cts, linked=linked, ft=ft)
         finally:
             c_oracle.set_progress(None)
     return buf, cts, time.time() - t0
 
 
-def _compare(lib, ctx, wit, seed, linked, capsys, name):
+def _compare(lib, ctx, wit, seed, linked, capsys, name, ft=False):
     tr = lib.Transcript(seed)
-    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr, linked=linked)
+    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr, linked=linked, ft=ft)
     ctx.trim()
-    buf, cts, took = _oracle_prove(wit, seed, linked, capsys, name)
+    buf, cts, took = _oracle_prove(wit, seed, linked, capsys, name, ft=ft)
     assert len(got["proof"]) == len(buf)
     assert got["proof"] == buf
     if linked:
@@ -84,6 +84,12 @@ def test_config3_linked_byte_exact(lib, ctx, capsys):
     re-indexing, merges on the stacks)."""
     wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)
     _compare(lib, ctx, wit, CONFIG_SEED + 4, True, capsys, "config 3 linked")
+
+
+def test_config3_ft_byte_exact(lib, ctx, capsys):
+    """The same window with the matrix products in the optimized aggregated form (f_t for the stack rounds)."""
+    wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)
+    _compare(lib, ctx, wit, CONFIG_SEED + 7, False, capsys, "config 3 ft", ft=True)
 
 
 def _budget_or_skip(factor, limit_s, name):
