@@ -400,6 +400,45 @@ int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_trans
                            size_t* proof_len, zkdl_fr* points_out, size_t* npoints, zkdl_claim* claims_out,
                            size_t* nclaims);
 
+/* ---- commitments (Sec. 2.3; Sec. 1.1; Protocol zkdl, the commit and proof-of-evaluation lines) ----
+ * Pedersen commitments in G1 of BLS12-381 (y^2 = x^3 + 4 over F_q, the subgroup of order r),
+ *   Commit(S; rho) = rho H + sum_i S_i G_i,
+ * and the row-wise commitment of a tensor: 2^m entries laid out as R = 2^ceil(m/2) rows of C = 2^floor(m/2)
+ * columns (row index = the leading variables), row j committed with the generators G_0..G_{C-1} and its own
+ * blinding rho_j, so that the commitment has O(sqrt(size)) group elements.
+ * A group element crosses the boundary as 96 bytes: affine x then y, 48 bytes little-endian each, fully
+ * reduced, not in Montgomery form; the identity as 96 zero bytes.
+ *
+ * zkdl_commit_key_create: the C = ncols generators and H of `label` (NUL-terminated, at most 16 bytes) and
+ * their window tables, in device memory.  Generator i: for ctr = 0, 1, .. the candidate
+ * x = int_be(SHA256(tag || u32be(i) || u32be(ctr) || 0x00) || SHA256(.. || 0x01)) mod q with
+ * tag = "zkdl-mi355x/g1/" || label; the first x for which x^3 + 4 is a square gives (x, y) with the smaller
+ * root y, multiplied by the cofactor (a candidate that becomes the identity is skipped); H is index
+ * 0xFFFFFFFF.  ncols a power of two up to 2^15; max_bits 32 or 64: the widest tensor entry the key serves
+ * (the tables hold 15 multiples per 4-bit window and generator: 168 B x 15 x max_bits / 4 per generator).
+ * zkdl_commit_key_generators: generators first .. first + count - 1 (index ncols = H) as bytes, for checks. */
+typedef struct zkdl_commit_key zkdl_commit_key;
+int zkdl_commit_key_create(zkdl_ctx* ctx, const char* label, uint64_t ncols, int max_bits, zkdl_commit_key** out);
+int zkdl_commit_key_destroy(zkdl_ctx* ctx, zkdl_commit_key* key);
+int zkdl_commit_key_generators(zkdl_ctx* ctx, const zkdl_commit_key* key, uint64_t first, uint64_t count,
+                               uint8_t* host_out);
+/* hyrax_commit: the R row commitments of X, an int32 or int64 tensor view (zkdl_tensor_wrap_int) of 2^m
+ * entries with C <= the key's ncols (int64 needs a key made with max_bits = 64); a negative entry x is the
+ * field element r - |x|, i.e. contributes -|x| G_i.  blind (host, R canonical elements, or NULL for zero
+ * blinding).  commitments_out (host, R x 96 bytes); *ncommit = capacity in elements on entry, R on return
+ * (ZKDL_ESMALL with *ncommit = R if too small). */
+int hyrax_commit(zkdl_ctx* ctx, const zkdl_commit_key* key, const zkdl_tensor* X, const zkdl_fr* blind,
+                 uint8_t* commitments_out, size_t* ncommit);
+/* hyrax_open: the prover's message of the proof of evaluation of X~ at `point` (host, m canonical
+ * elements, row coordinates first): T = sum_j beta~(v_row, j) X[j, :] (T_out, C elements),
+ * rho* = sum_j beta~(v_row, j) rho_j (rho_out, may be NULL) and y = <T, beta~(v_col, .)> = X~(point).
+ * The verifier combines the row commitments with the same weights (the homomorphism of Sec. 2.3) and
+ * checks Commit(T; rho*) against the result and y against T.  X: any tensor of 2^m entries. */
+int hyrax_open(zkdl_ctx* ctx, const zkdl_tensor* X, const zkdl_fr* blind, const zkdl_fr* point, size_t npoint,
+               zkdl_fr* T_out, zkdl_fr* rho_out, zkdl_fr* y_out);
+/* Re-derives the constants of the base-field arithmetic on the host; ZKDL_OK if they match. */
+int zkdl_commit_selfcheck(void);
+
 /* ---- per-kernel timing (for callers that measure; paper-independent) -------
  * While enabled, the launches of the kernel classes below are bracketed by HIP
  * events on the context's stream; zkdl_ctx_profile_read returns, per class and

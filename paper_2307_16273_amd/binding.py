@@ -21,6 +21,8 @@ EXPORTED_SYMBOLS = [
     "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_hadamard",
     "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "aggregate_prove_ft", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read", "zkdl_selfbench",
+    "zkdl_commit_key_create", "zkdl_commit_key_destroy", "zkdl_commit_key_generators", "hyrax_commit", "hyrax_open",
+    "zkdl_commit_selfcheck",
 ]
 
 PROF_CLASSES = {"sc_round_fused": 0, "sc_round_first": 1, "partial_eval": 2, "zk_bin": 3, "zk_lin": 4,
@@ -94,6 +96,10 @@ def load_library():
         "zkdl_ctx_profile_enable": [vp, i], "zkdl_ctx_profile_reset": [vp],
         "zkdl_ctx_profile_read": [vp, i, C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
         "zkdl_selfbench": [vp, i, u64, C.POINTER(C.c_double), C.POINTER(C.c_double)],
+        "zkdl_commit_key_create": [vp, C.c_char_p, u64, i, pp], "zkdl_commit_key_destroy": [vp, vp],
+        "zkdl_commit_key_generators": [vp, vp, u64, u64, vp],
+        "hyrax_commit": [vp, vp, vp, vp, vp, psz], "hyrax_open": [vp, vp, vp, vp, sz, vp, vp, vp],
+        "zkdl_commit_selfcheck": [],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -455,3 +461,60 @@ def host_fr_mul(a, b):
 
 def selfcheck_constants():
     return load_library().zkdl_selfcheck_constants()
+
+
+class CommitKey:
+    """Generators and window tables of the row-wise Pedersen commitment (device memory)."""
+
+    def __init__(self, ctx, label, ncols, max_bits=32):
+        self.ctx = ctx
+        self.ncols = ncols
+        self.handle = C.c_void_p()
+        _check(load_library().zkdl_commit_key_create(ctx.handle, bytes(label), ncols, max_bits, C.byref(self.handle)),
+               "zkdl_commit_key_create", ctx)
+
+    def generators(self, first, count):
+        """`count` generators from index `first` (index ncols is H), 96 bytes each."""
+        out = C.create_string_buffer(96 * count)
+        _check(load_library().zkdl_commit_key_generators(self.ctx.handle, self.handle, first, count, out),
+               "zkdl_commit_key_generators", self.ctx)
+        return [out.raw[96 * k:96 * k + 96] for k in range(count)]
+
+    def close(self):
+        if self.handle:
+            load_library().zkdl_commit_key_destroy(self.ctx.handle, self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def hyrax_commit(ctx, key, x, blind=None):
+    """x: an int32 / int64 tensor view; blind: None or one field element per row.  Returns the row
+    commitments, 96 bytes each."""
+    m = x.numel.bit_length() - 1
+    rows = 1 << (m - m // 2)
+    out = C.create_string_buffer(96 * rows)
+    n = C.c_size_t(rows)
+    bb = C.create_string_buffer(_fr_bytes(blind), 32 * rows) if blind is not None else None
+    _check(load_library().hyrax_commit(ctx.handle, key.handle, x.handle, bb, out, C.byref(n)), "hyrax_commit", ctx)
+    return [out.raw[96 * k:96 * k + 96] for k in range(n.value)]
+
+
+def hyrax_open(ctx, x, blind, point):
+    """Returns (T, rho*, y) as integers."""
+    m = x.numel.bit_length() - 1
+    rows, cols = 1 << (m - m // 2), 1 << (m // 2)
+    t = C.create_string_buffer(32 * cols)
+    rho, y = C.create_string_buffer(32), C.create_string_buffer(32)
+    bb = C.create_string_buffer(_fr_bytes(blind), 32 * rows) if blind is not None else None
+    pb = C.create_string_buffer(_fr_bytes(point), max(32 * len(point), 1))
+    _check(load_library().hyrax_open(ctx.handle, x.handle, bb, pb, len(point), t, rho, y), "hyrax_open", ctx)
+    return _split_fr(t.raw, cols), int.from_bytes(rho.raw, "little"), int.from_bytes(y.raw, "little")
+
+
+def commit_selfcheck():
+    return load_library().zkdl_commit_selfcheck()

@@ -661,6 +661,44 @@ extern "C" int mle_partial_eval(zkdl_ctx* ctx, const zkdl_tensor* t, int axis_lo
 }
 
 // ---------------------------------------------------------------------------
+// hyrax_open: the prover's side of the proof of evaluation for a tensor committed row by row
+// (Sec. 2.3; Protocol zkdl, the proof-of-evaluation line): three partial evaluations
+// ---------------------------------------------------------------------------
+extern "C" int hyrax_open(zkdl_ctx* ctx, const zkdl_tensor* X, const zkdl_fr* blind, const zkdl_fr* point,
+                          size_t npoint, zkdl_fr* T_out, zkdl_fr* rho_out, zkdl_fr* y_out) {
+    if (!ctx || !X || !T_out || !y_out || (npoint && !point)) return ZKDL_EINVAL;
+    const int m = ilog2_u64(X->numel);
+    if (!is_pow2(X->numel) || (size_t)m != npoint) return ZKDL_EINVAL;
+    for (size_t i = 0; i < npoint; ++i)
+        if (!fr_bytes_canonical(point[i].le)) return ZKDL_EINVAL;
+    const uint64_t cols = (uint64_t)1 << (m / 2), rows = (uint64_t)1 << (m - m / 2);
+    const int lr = m - m / 2;
+    zkdl_tensor view = *X;   // the same memory as an R x C matrix
+    view.ndim = 2;
+    view.shape[0] = rows;
+    view.shape[1] = cols;
+    view.owned = false;
+    zkdl_tensor *t = nullptr, *y = nullptr, *b = nullptr, *r = nullptr;
+    int rc = mle_partial_eval(ctx, &view, 0, 1, point, (size_t)lr, &t);          // T = sum_j beta~(v_row, j) X[j, :]
+    if (rc == ZKDL_OK) rc = mle_partial_eval(ctx, t, 0, 1, point + lr, npoint - (size_t)lr, &y);   // <T, beta~(v_col, .)>
+    if (rc == ZKDL_OK) rc = zkdl_tensor_download(ctx, t, T_out);
+    if (rc == ZKDL_OK) rc = zkdl_tensor_download(ctx, y, y_out);
+    if (rc == ZKDL_OK && blind && rho_out) {                                       // rho* = sum_j beta~(v_row, j) rho_j
+        const uint64_t shape[1] = {rows};
+        rc = fr_tensor_upload(ctx, blind, ZKDL_FR_LE, 0, shape, 1, &b);
+        if (rc == ZKDL_OK) rc = mle_partial_eval(ctx, b, 0, 1, point, (size_t)lr, &r);
+        if (rc == ZKDL_OK) rc = zkdl_tensor_download(ctx, r, rho_out);
+    } else if (rc == ZKDL_OK && rho_out) {
+        memset(rho_out->le, 0, 32);
+    }
+    if (t) zkdl_tensor_free(ctx, t);
+    if (y) zkdl_tensor_free(ctx, y);
+    if (b) zkdl_tensor_free(ctx, b);
+    if (r) zkdl_tensor_free(ctx, r);
+    return rc;
+}
+
+// ---------------------------------------------------------------------------
 // sumcheck_product
 // ---------------------------------------------------------------------------
 extern "C" int sumcheck_product(zkdl_ctx* ctx, const zkdl_tensor* const* tables, int K,

@@ -1,0 +1,314 @@
+// Arithmetic in F_q, the base field of BLS12-381 (q has 381 bits), and the group law of G1,
+// y^2 = x^3 + 4, for the Pedersen commitments of Sec. 2.3 (Sec. 6 names the curve).
+//
+// An element is a fully reduced residue in Montgomery form with R = 2^406, held as 14 limbs of
+// 29 bits: as for the scalar field, a 29 x 29-bit product is below 2^58, so a whole column of a product
+// (at most 14 operand and 13 reduction products) accumulates in one 64-bit register with plain
+// v_mad_u64_u32 and no carry handling.  q is not 1 modulo 2^29, so each column costs one extra
+// multiplication for the Montgomery factor.  Sums and differences are reduced at once (one conditional
+// subtraction or addition of q, selected without a branch): every value a kernel holds is the unique
+// representative below q.
+//
+// Points are in homogeneous projective coordinates (X : Y : Z), the identity (0 : 1 : 0), with the
+// complete addition and doubling formulas for curves of j-invariant 0 (Renes, Costello, Batina,
+// "Complete addition formulas for prime order elliptic curves", Algorithms 7 and 9 with b3 = 3 b = 12):
+// no case distinction for equal, opposite or neutral operands, so lanes never diverge inside a sum.
+#pragma once
+#include <stdint.h>
+#include <hip/hip_runtime.h>
+
+#define FQ_HD __host__ __device__ __forceinline__
+
+namespace fqc {
+constexpr int L = 14;
+constexpr uint32_t M29 = 0x1fffffffu;
+// q in 29-bit limbs
+constexpr uint32_t Q[L] = {0x1fffaaabu, 0x0ff7ffffu, 0x14ffffeeu, 0x17fffd62u, 0x0f6241eau, 0x09507b58u, 0x0afd9cc3u,
+                           0x109e70a2u, 0x1764774bu, 0x121a5d66u, 0x12c6e9edu, 0x12ffcd34u, 0x00111ea3u, 0x0000000du};
+constexpr uint32_t NINV = 0x1ffcfffdu;   // -q^{-1} mod 2^29
+// 2^406 mod q (Montgomery form of 1) and 2^812 mod q; re-derived by modular doubling in fq_selfcheck
+constexpr uint32_t ONE[L] = {0x03a9fb84u, 0x0ba00690u, 0x071288f1u, 0x0f59bcc5u, 0x126cb614u, 0x0585bf36u, 0x1b85ac3du,
+                             0x1cf856fau, 0x1891ecbdu, 0x1a7eec05u, 0x155a88f0u, 0x0741ac6du, 0x1317c30fu, 0x00000009u};
+constexpr uint32_t R2[L] = {0x15bef7aeu, 0x1031cd0eu, 0x02dd93e8u, 0x09226323u, 0x0e6e2cd2u, 0x11684daau, 0x1170e5dbu,
+                            0x088e25b1u, 0x1b366399u, 0x1c536f47u, 0x0d1f9cbcu, 0x0278b67fu, 0x1ea66a2bu, 0x0000000cu};
+// exponents as 32-bit words, least significant first: (q + 1) / 4 (square roots: q = 3 mod 4) and q - 2
+constexpr uint32_t EXP_SQRT[12] = {0xffffeaabu, 0xee7fbfffu, 0xac54ffffu, 0x07aaffffu, 0x3dac3d89u, 0xd9cc34a8u,
+                                   0x3ce144afu, 0xd91dd2e1u, 0x90d2eb35u, 0x92c6e9edu, 0x8e5ff9a6u, 0x0680447au};
+constexpr uint32_t EXP_INV[12] = {0xffffaaa9u, 0xb9feffffu, 0xb153ffffu, 0x1eabfffeu, 0xf6b0f624u, 0x6730d2a0u,
+                                  0xf38512bfu, 0x64774b84u, 0x434bacd7u, 0x4b1ba7b6u, 0x397fe69au, 0x1a0111eau};
+// the cofactor of G1 (the curve has COFACTOR * r points)
+constexpr uint32_t COFACTOR[4] = {0x0000aaabu, 0x8c00aaabu, 0x5555e156u, 0x396c8c00u};
+}  // namespace fqc
+
+struct Fq {
+    uint32_t v[fqc::L];
+};
+
+FQ_HD Fq fq_zero() {
+    Fq z;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) z.v[i] = 0;
+    return z;
+}
+
+FQ_HD Fq fq_const(const uint32_t (&c)[fqc::L]) {
+    Fq z;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) z.v[i] = c[i];
+    return z;
+}
+
+FQ_HD Fq fq_one() { return fq_const(fqc::ONE); }
+
+FQ_HD bool fq_is_zero(const Fq& a) {
+    uint32_t o = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) o |= a.v[i];
+    return o == 0;
+}
+
+FQ_HD bool fq_eq(const Fq& a, const Fq& b) {
+    uint32_t o = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) o |= a.v[i] ^ b.v[i];
+    return o == 0;
+}
+
+// t - q if t >= q else t, for normal limbs and t < 2q
+FQ_HD Fq fq_cond_sub(const Fq& t) {
+    Fq d;
+    int32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        int32_t x = (int32_t)t.v[i] - (int32_t)fqc::Q[i] + c;
+        d.v[i] = (uint32_t)x & fqc::M29;
+        c = x >> 29;   // 0 or -1
+    }
+    Fq o;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) o.v[i] = c < 0 ? t.v[i] : d.v[i];
+    return o;
+}
+
+FQ_HD Fq fq_add(const Fq& a, const Fq& b) {
+    Fq t;
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        uint32_t x = a.v[i] + b.v[i] + c;
+        t.v[i] = i < fqc::L - 1 ? (x & fqc::M29) : x;   // the sum is below 2q < 2^382: the top limb holds it
+        c = i < fqc::L - 1 ? (x >> 29) : 0;
+    }
+    return fq_cond_sub(t);
+}
+
+FQ_HD Fq fq_sub(const Fq& a, const Fq& b) {
+    Fq d;
+    int32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        int32_t x = (int32_t)a.v[i] - (int32_t)b.v[i] + c;
+        d.v[i] = (uint32_t)x & fqc::M29;
+        c = x >> 29;
+    }
+    // c < 0: the difference is negative (its limbs hold it modulo 2^406): add q back
+    Fq e;
+    uint32_t k = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        uint32_t x = d.v[i] + fqc::Q[i] + k;
+        e.v[i] = x & fqc::M29;
+        k = x >> 29;
+    }
+    Fq o;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) o.v[i] = c < 0 ? e.v[i] : d.v[i];
+    return o;
+}
+
+FQ_HD Fq fq_neg(const Fq& a) { return fq_sub(fq_zero(), a); }
+
+// Montgomery product a b / 2^406 mod q, fully reduced; a, b below q
+FQ_HD Fq fq_mul(const Fq& a, const Fq& b) {
+    uint64_t acc = 0;
+    uint32_t m[fqc::L];
+    Fq t;
+#pragma unroll
+    for (int k = 0; k < 2 * fqc::L - 1; ++k) {
+        const int lo_i = k < fqc::L ? 0 : k - (fqc::L - 1), hi_i = k < fqc::L ? k : fqc::L - 1;
+#pragma unroll
+        for (int i = lo_i; i <= hi_i; ++i) acc += (uint64_t)a.v[i] * b.v[k - i];
+#pragma unroll
+        for (int i = lo_i; i <= hi_i; ++i)
+            if (k - i >= 1) acc += (uint64_t)m[i] * fqc::Q[k - i];
+        if (k < fqc::L) {
+            m[k] = ((uint32_t)acc * fqc::NINV) & fqc::M29;   // makes the low 29 bits of the column vanish
+            acc += (uint64_t)m[k] * fqc::Q[0];
+        } else {
+            t.v[k - fqc::L] = (uint32_t)acc & fqc::M29;
+        }
+        acc >>= 29;
+    }
+    t.v[fqc::L - 1] = (uint32_t)acc;
+    return fq_cond_sub(t);   // a b / R + q < 2q
+}
+
+FQ_HD Fq fq_sqr(const Fq& a) { return fq_mul(a, a); }
+
+// a^e, e given as `words` 32-bit words, least significant first
+template <int WORDS>
+FQ_HD Fq fq_pow(const Fq& a, const uint32_t (&e)[WORDS]) {
+    Fq acc = fq_one();
+    for (int w = WORDS - 1; w >= 0; --w)
+        for (int bit = 31; bit >= 0; --bit) {
+            acc = fq_sqr(acc);
+            if ((e[w] >> bit) & 1u) acc = fq_mul(acc, a);
+        }
+    return acc;
+}
+
+FQ_HD Fq fq_inv(const Fq& a) { return fq_pow(a, fqc::EXP_INV); }
+
+// 48 little-endian bytes (any value below 2^384) -> normal limbs of the plain value
+FQ_HD Fq fq_limbs_from_bytes(const uint8_t* p) {
+    Fq o;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        uint64_t w = 0;
+        const int bit = 29 * i, byte = bit >> 3, sh = bit & 7;
+#pragma unroll
+        for (int b = 0; b < 5; ++b)
+            if (byte + b < 48) w |= (uint64_t)p[byte + b] << (8 * b);
+        o.v[i] = (uint32_t)(w >> sh) & fqc::M29;
+    }
+    return o;
+}
+
+// plain value below q as 48 little-endian bytes
+FQ_HD void fq_limbs_to_bytes(const Fq& a, uint8_t* p) {
+    for (int b = 0; b < 48; ++b) p[b] = 0;
+    for (int i = 0; i < fqc::L; ++i) {
+        const int bit = 29 * i, byte = bit >> 3, sh = bit & 7;
+        uint64_t w = (uint64_t)a.v[i] << sh;
+        for (int b = 0; b < 5; ++b)
+            if (byte + b < 48) p[byte + b] |= (uint8_t)(w >> (8 * b));
+    }
+}
+
+FQ_HD Fq fq_to_mont(const Fq& plain) { return fq_mul(plain, fq_const(fqc::R2)); }   // plain below q
+
+FQ_HD Fq fq_from_mont(const Fq& a) {
+    Fq one = fq_zero();
+    one.v[0] = 1;
+    return fq_mul(a, one);
+}
+
+// a value below 2^384 given as normal limbs, reduced modulo q into Montgomery form: the Montgomery product
+// with 2^812 tolerates any first operand whose limbs are normal (a b / R + q < 2q still holds for a < 2^406)
+FQ_HD Fq fq_reduce_to_mont(const Fq& any) { return fq_mul(any, fq_const(fqc::R2)); }
+
+// ---- G1 -------------------------------------------------------------------------------------------
+struct G1 {
+    Fq X, Y, Z;
+};
+
+FQ_HD G1 g1_identity() {
+    G1 p;
+    p.X = fq_zero();
+    p.Y = fq_one();
+    p.Z = fq_zero();
+    return p;
+}
+
+FQ_HD Fq fq_mul12(const Fq& a) {   // b3 = 3 b = 12
+    Fq t = fq_add(a, a);
+    t = fq_add(t, a);
+    t = fq_add(t, t);
+    return fq_add(t, t);
+}
+
+// complete addition (Algorithm 7 of the reference above, a = 0)
+FQ_HD G1 g1_add(const G1& p, const G1& q) {
+    Fq t0 = fq_mul(p.X, q.X), t1 = fq_mul(p.Y, q.Y), t2 = fq_mul(p.Z, q.Z);
+    Fq t3 = fq_mul(fq_add(p.X, p.Y), fq_add(q.X, q.Y));
+    t3 = fq_sub(t3, fq_add(t0, t1));
+    Fq t4 = fq_mul(fq_add(p.Y, p.Z), fq_add(q.Y, q.Z));
+    t4 = fq_sub(t4, fq_add(t1, t2));
+    Fq y3 = fq_mul(fq_add(p.X, p.Z), fq_add(q.X, q.Z));
+    y3 = fq_sub(y3, fq_add(t0, t2));
+    Fq x3 = fq_add(t0, t0);
+    t0 = fq_add(x3, t0);
+    t2 = fq_mul12(t2);
+    Fq z3 = fq_add(t1, t2);
+    t1 = fq_sub(t1, t2);
+    y3 = fq_mul12(y3);
+    x3 = fq_mul(t4, y3);
+    t2 = fq_mul(t3, t1);
+    x3 = fq_sub(t2, x3);
+    y3 = fq_mul(y3, t0);
+    t1 = fq_mul(t1, z3);
+    y3 = fq_add(t1, y3);
+    t0 = fq_mul(t0, t3);
+    z3 = fq_mul(z3, t4);
+    z3 = fq_add(z3, t0);
+    G1 r;
+    r.X = x3;
+    r.Y = y3;
+    r.Z = z3;
+    return r;
+}
+
+// doubling (Algorithm 9, a = 0)
+FQ_HD G1 g1_dbl(const G1& p) {
+    Fq t0 = fq_sqr(p.Y);
+    Fq z3 = fq_add(t0, t0);
+    z3 = fq_add(z3, z3);
+    z3 = fq_add(z3, z3);
+    Fq t1 = fq_mul(p.Y, p.Z);
+    Fq t2 = fq_mul12(fq_sqr(p.Z));
+    Fq x3 = fq_mul(t2, z3);
+    Fq y3 = fq_add(t0, t2);
+    z3 = fq_mul(t1, z3);
+    t1 = fq_add(t2, t2);
+    t2 = fq_add(t1, t2);
+    t0 = fq_sub(t0, t2);
+    y3 = fq_mul(t0, y3);
+    y3 = fq_add(x3, y3);
+    t1 = fq_mul(p.X, p.Y);
+    x3 = fq_mul(t0, t1);
+    x3 = fq_add(x3, x3);
+    G1 r;
+    r.X = x3;
+    r.Y = y3;
+    r.Z = z3;
+    return r;
+}
+
+FQ_HD G1 g1_neg(const G1& p) {
+    G1 r = p;
+    r.Y = fq_neg(p.Y);
+    return r;
+}
+
+// k P for a scalar of `WORDS` 32-bit words (least significant first), double-and-add from the top bit
+template <int WORDS>
+FQ_HD G1 g1_mul_words(const G1& p, const uint32_t (&k)[WORDS]) {
+    G1 acc = g1_identity();
+    for (int w = WORDS - 1; w >= 0; --w)
+        for (int bit = 31; bit >= 0; --bit) {
+            acc = g1_dbl(acc);
+            if ((k[w] >> bit) & 1u) acc = g1_add(acc, p);
+        }
+    return acc;
+}
+
+// affine (x, y) as 2 x 48 little-endian bytes of the plain values; the identity as 96 zero bytes
+FQ_HD void g1_to_bytes(const G1& p, uint8_t* out) {
+    if (fq_is_zero(p.Z)) {
+        for (int b = 0; b < 96; ++b) out[b] = 0;
+        return;
+    }
+    const Fq zi = fq_inv(p.Z);
+    fq_limbs_to_bytes(fq_from_mont(fq_mul(p.X, zi)), out);
+    fq_limbs_to_bytes(fq_from_mont(fq_mul(p.Y, zi)), out + 48);
+}

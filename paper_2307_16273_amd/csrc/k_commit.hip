@@ -1,0 +1,318 @@
+// Pedersen commitments on G1 of BLS12-381 and the row-wise commitment of a tensor (Sec. 2.3; Sec. 1.1;
+// Protocol zkdl, the commit and proof-of-evaluation lines).
+//
+//   Commit(S; rho) = rho H + sum_i S_i G_i                                   (Sec. 2.3, additive notation)
+//
+// A tensor of 2^m quantised integers is laid out as R = 2^ceil(m/2) rows of C = 2^floor(m/2) columns and
+// every row is committed with the same C generators and its own blinding scalar: the commitment has
+// R = O(sqrt(size)) group elements (Sec. 1.1).  Generators are derived from a label by hashing to the
+// curve (try-and-increment on SHA-256, cofactor cleared), so nobody knows a relation between them.
+//
+// Scalars are small: tensors are 32-bit (activations, weights, gradients) or 64-bit (pre-activations)
+// signed integers, a negative entry x being the field element r - |x|, i.e. -|x| G.  The sum therefore
+// runs over fixed-base window tables: for every generator the multiples d 2^(4k) G, d = 1..15, k < bits/4,
+// are built once with the key, and a commitment is a plain sum of one table entry per non-zero 4-bit digit
+// of |x| - no doublings and no buckets.  The blinding term rho H (rho a full field element) uses the same
+// kind of table with 64 windows.  All sums use the complete projective formulas of fq.cuh.
+#include <string.h>
+#include <new>
+
+#include "zkdl_internal.h"
+#include "fq.cuh"
+
+namespace {
+
+constexpr int CK_DIGITS = 15;        // table entries per window: d = 1..15
+constexpr int CK_CHUNK = 32;         // columns summed by one thread
+constexpr int CK_H_WINDOWS = 64;     // 4-bit windows of a 255-bit blinding scalar
+constexpr int CK_MAX_LABEL = 16;
+
+struct LabelArg {
+    uint8_t bytes[15 + CK_MAX_LABEL];   // "zkdl-mi355x/g1/" followed by the label
+    uint32_t len;
+};
+
+// 2^384 * 2^812 mod q: brings the top 128 bits of a 512-bit hash into Montgomery form
+// (fq_mul(hi, R2X) = hi 2^384 R mod q); checked against repeated doubling in zk_commit_selfcheck
+__device__ __host__ inline Fq r2x_const() {
+    Fq c = fq_const(fqc::R2);
+    for (int i = 0; i < 384; ++i) c = fq_add(c, c);
+    return c;
+}
+
+__device__ inline void sha_one_block(const uint8_t* msg, uint32_t len, uint32_t out[8]) {   // len <= 55
+    uint32_t w[16];
+    for (int i = 0; i < 16; ++i) w[i] = 0;
+    for (uint32_t i = 0; i < len; ++i) w[i >> 2] |= (uint32_t)msg[i] << (24 - 8 * (i & 3));
+    w[len >> 2] |= 0x80u << (24 - 8 * (len & 3));
+    w[15] = len * 8;
+    uint32_t h[8] = {0x6a09e667u, 0xbb67ae85u, 0x3c6ef372u, 0xa54ff53au, 0x510e527fu, 0x9b05688cu, 0x1f83d9abu, 0x5be0cd19u};
+    sha::compress(h, w);
+    for (int i = 0; i < 8; ++i) out[i] = h[i];
+}
+
+// plain a < plain b ?  (both below q, plain limbs)
+__device__ inline bool limbs_less(const Fq& a, const Fq& b) {
+    for (int i = fqc::L - 1; i >= 0; --i) {
+        if (a.v[i] != b.v[i]) return a.v[i] < b.v[i];
+    }
+    return false;
+}
+
+// Generator `index` of the label: for ctr = 0, 1, .. the candidate x = int_be(SHA256(tag || u32be(index) ||
+// u32be(ctr) || 0) || SHA256(.. || 1)) mod q; the first x for which x^3 + 4 is a square gives (x, y) with the
+// smaller root y; cleared of the cofactor; a candidate that becomes the identity is skipped.
+__global__ __launch_bounds__(64) void k_ck_generators(LabelArg label, uint64_t ncols, G1* gens, Fq r2x) {
+    const uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (i > ncols) return;
+    const uint32_t index = i < ncols ? (uint32_t)i : 0xFFFFFFFFu;   // the last one is the blinding generator H
+    uint8_t msg[56];
+    for (uint32_t b = 0; b < label.len; ++b) msg[b] = label.bytes[b];
+    uint32_t at = label.len;
+    for (int b = 0; b < 4; ++b) msg[at + b] = (uint8_t)(index >> (24 - 8 * b));
+    at += 8;
+    Fq four = fq_add(fq_one(), fq_one());
+    four = fq_add(four, four);
+    for (uint32_t ctr = 0;; ++ctr) {
+        for (int b = 0; b < 4; ++b) msg[at - 4 + b] = (uint8_t)(ctr >> (24 - 8 * b));
+        uint32_t dg[16];
+        msg[at] = 0;
+        sha_one_block(msg, at + 1, dg);
+        msg[at] = 1;
+        sha_one_block(msg, at + 1, dg + 8);
+        // the 64 digest bytes as a big-endian integer: little-endian byte k is byte 63 - k of the digests
+        uint8_t le[64];
+        for (int k = 0; k < 64; ++k) {
+            const int pos = 63 - k;
+            le[k] = (uint8_t)(dg[pos >> 2] >> (24 - 8 * (pos & 3)));
+        }
+        uint8_t hi48[48];
+        for (int k = 0; k < 48; ++k) hi48[k] = k < 16 ? le[48 + k] : 0;
+        const Fq x = fq_add(fq_reduce_to_mont(fq_limbs_from_bytes(le)), fq_mul(fq_limbs_from_bytes(hi48), r2x));
+        const Fq rhs = fq_add(fq_mul(fq_sqr(x), x), four);
+        Fq y = fq_pow(rhs, fqc::EXP_SQRT);
+        if (!fq_eq(fq_sqr(y), rhs)) continue;
+        const Fq yn = fq_neg(y);
+        if (limbs_less(fq_from_mont(yn), fq_from_mont(y))) y = yn;
+        G1 p;
+        p.X = x;
+        p.Y = y;
+        p.Z = fq_one();
+        p = g1_mul_words(p, fqc::COFACTOR);
+        if (fq_is_zero(p.Z)) continue;
+        gens[i] = p;
+        return;
+    }
+}
+
+// table[(g * windows + k) * 15 + d - 1] = d 2^(4k) gens[g]
+__global__ __launch_bounds__(64) void k_ck_tables(const G1* gens, uint64_t ngens, int windows, G1* table) {
+    const uint64_t t = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (t >= ngens * (uint64_t)windows) return;
+    const uint64_t g = t / windows;
+    const int k = (int)(t % windows);
+    G1 base = gens[g];
+    for (int s = 0; s < 4 * k; ++s) base = g1_dbl(base);
+    G1* out = table + t * CK_DIGITS;
+    G1 acc = base;
+    out[0] = acc;
+    for (int d = 2; d <= CK_DIGITS; ++d) {
+        acc = g1_add(acc, base);
+        out[d - 1] = acc;
+    }
+}
+
+// part[row * nchunk + q] = sum over the columns of chunk q of x[row, c] G_c, from the window tables
+template <typename INT>
+__global__ __launch_bounds__(64) void k_commit_partial(const INT* x, uint64_t rows, uint64_t cols, uint64_t nchunk, int windows,
+                                                       const G1* table, G1* part) {
+    const uint64_t t = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (t >= rows * nchunk) return;
+    const uint64_t row = t / nchunk, q = t % nchunk;
+    const uint64_t c0 = q * CK_CHUNK, c1 = c0 + CK_CHUNK < cols ? c0 + CK_CHUNK : cols;
+    G1 acc = g1_identity();
+    for (uint64_t c = c0; c < c1; ++c) {
+        const INT s = x[row * cols + c];
+        const bool negative = s < 0;
+        uint64_t mag = negative ? (uint64_t)0 - (uint64_t)(int64_t)s : (uint64_t)s;
+        for (int k = 0; k < windows && mag != 0; ++k, mag >>= 4) {
+            const uint32_t d = (uint32_t)mag & 15u;
+            if (d == 0) continue;
+            G1 p = table[(c * (uint64_t)windows + k) * CK_DIGITS + d - 1];
+            if (negative) p.Y = fq_neg(p.Y);   // x = r - |x| as a field element: -|x| G
+            acc = g1_add(acc, p);
+        }
+    }
+    part[t] = acc;
+}
+
+// row commitment = sum of its partial sums + rho_row H, written as affine bytes
+__global__ __launch_bounds__(64) void k_commit_finish(const G1* part, uint64_t rows, uint64_t nchunk, const uint32_t* rho_le,
+                                                      const G1* h_table, uint8_t* out) {
+    const uint64_t row = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (row >= rows) return;
+    G1 acc = part[row * nchunk];
+    for (uint64_t q = 1; q < nchunk; ++q) acc = g1_add(acc, part[row * nchunk + q]);
+    if (rho_le) {
+        for (int k = 0; k < CK_H_WINDOWS; ++k) {
+            const uint32_t d = (rho_le[row * 8 + (k >> 3)] >> (4 * (k & 7))) & 15u;
+            if (d) acc = g1_add(acc, h_table[k * CK_DIGITS + d - 1]);
+        }
+    }
+    g1_to_bytes(acc, out + row * 96);
+}
+
+__global__ __launch_bounds__(64) void k_ck_export(const G1* gens, uint64_t first, uint64_t count, uint8_t* out) {
+    const uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    g1_to_bytes(gens[first + i], out + i * 96);
+}
+
+}  // namespace
+
+struct zkdl_commit_key {
+    uint64_t ncols;
+    int windows;      // 4-bit windows of a tensor entry: 8 (32-bit) or 16 (64-bit)
+    G1* gens;         // device: ncols generators, then H
+    G1* table;        // device: [ncols][windows][15]
+    G1* h_table;      // device: [64][15]
+};
+
+// host-side check of the constants of fq.cuh (no GPU needed): Montgomery one and R^2 by repeated doubling,
+// the Montgomery factor, the square-root and inversion exponents
+extern "C" int zkdl_commit_selfcheck(void) {
+    Fq x = fq_zero();
+    x.v[0] = 1;
+    for (int i = 0; i < 406; ++i) x = fq_add(x, x);
+    if (!fq_eq(x, fq_const(fqc::ONE))) return ZKDL_EINVAL;
+    for (int i = 0; i < 406; ++i) x = fq_add(x, x);
+    if (!fq_eq(x, fq_const(fqc::R2))) return ZKDL_EINVAL;
+    if (((fqc::Q[0] * fqc::NINV) & fqc::M29) != fqc::M29) return ZKDL_EINVAL;   // q * (-q^{-1}) = -1 mod 2^29
+    // 3^(q-2) * 3 = 1 and (3^2)^((q+1)/4) = +-3
+    Fq three = fq_add(fq_one(), fq_add(fq_one(), fq_one()));
+    if (!fq_eq(fq_mul(fq_inv(three), three), fq_one())) return ZKDL_EINVAL;
+    Fq root = fq_pow(fq_sqr(three), fqc::EXP_SQRT);
+    if (!fq_eq(root, three) && !fq_eq(root, fq_neg(three))) return ZKDL_EINVAL;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_commit_key_destroy(zkdl_ctx* ctx, zkdl_commit_key* key) {
+    if (!ctx || !key) return ZKDL_EINVAL;
+    (void)hipStreamSynchronize(ctx->stream);
+    zk_free(ctx, key->gens);
+    zk_free(ctx, key->table);
+    zk_free(ctx, key->h_table);
+    delete key;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_commit_key_create(zkdl_ctx* ctx, const char* label, uint64_t ncols, int max_bits,
+                                      zkdl_commit_key** out) {
+    if (!ctx || !label || !out || (max_bits != 32 && max_bits != 64)) return ZKDL_EINVAL;
+    const size_t ll = strlen(label);
+    if (ll > (size_t)CK_MAX_LABEL || ncols == 0 || (ncols & (ncols - 1)) || ncols > ((uint64_t)1 << 15)) return ZKDL_EINVAL;
+    if (zkdl_commit_selfcheck() != ZKDL_OK) return ZKDL_EINVAL;
+    ZK_HIP(ctx, hipSetDevice(ctx->device));
+    zkdl_commit_key* key = new (std::nothrow) zkdl_commit_key();
+    if (!key) return ZKDL_ENOMEM;
+    key->ncols = ncols;
+    key->windows = max_bits / 4;
+    key->gens = (G1*)zk_alloc(ctx, sizeof(G1) * (ncols + 1));
+    key->table = (G1*)zk_alloc(ctx, sizeof(G1) * ncols * key->windows * CK_DIGITS);
+    key->h_table = (G1*)zk_alloc(ctx, sizeof(G1) * CK_H_WINDOWS * CK_DIGITS);
+    if (!key->gens || !key->table || !key->h_table) {
+        zkdl_commit_key_destroy(ctx, key);
+        return ZKDL_ENOMEM;
+    }
+    LabelArg la;
+    memcpy(la.bytes, "zkdl-mi355x/g1/", 15);
+    memcpy(la.bytes + 15, label, ll);
+    la.len = (uint32_t)(15 + ll);
+    const Fq r2x = r2x_const();
+    hipLaunchKernelGGL(k_ck_generators, dim3((unsigned)((ncols + 1 + 63) / 64)), dim3(64), 0, ctx->stream, la, ncols,
+                       key->gens, r2x);
+    const uint64_t nt = ncols * key->windows;
+    hipLaunchKernelGGL(k_ck_tables, dim3((unsigned)((nt + 63) / 64)), dim3(64), 0, ctx->stream, key->gens, ncols,
+                       key->windows, key->table);
+    hipLaunchKernelGGL(k_ck_tables, dim3(1), dim3(64), 0, ctx->stream, key->gens + ncols, (uint64_t)1, CK_H_WINDOWS,
+                       key->h_table);
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) {
+        ctx->last_hip = (int)e;
+        zkdl_commit_key_destroy(ctx, key);
+        return ZKDL_EHIP;
+    }
+    *out = key;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_commit_key_generators(zkdl_ctx* ctx, const zkdl_commit_key* key, uint64_t first, uint64_t count,
+                                          uint8_t* host_out) {
+    if (!ctx || !key || !host_out || first + count > key->ncols + 1 || count == 0) return ZKDL_EINVAL;
+    uint8_t* dev = (uint8_t*)zk_alloc(ctx, count * 96);
+    if (!dev) return ZKDL_ENOMEM;
+    hipLaunchKernelGGL(k_ck_export, dim3((unsigned)((count + 63) / 64)), dim3(64), 0, ctx->stream, key->gens, first, count, dev);
+    hipError_t e = hipMemcpyAsync(host_out, dev, count * 96, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    zk_free(ctx, dev);
+    ZK_HIP(ctx, e);
+    return ZKDL_OK;
+}
+
+extern "C" int hyrax_commit(zkdl_ctx* ctx, const zkdl_commit_key* key, const zkdl_tensor* X, const zkdl_fr* blind,
+                            uint8_t* commitments_out, size_t* ncommit) {
+    if (!ctx || !key || !X || !commitments_out || !ncommit) return ZKDL_EINVAL;
+    if (X->kind != TK_I32 && X->kind != TK_I64) return ZKDL_EINVAL;
+    if (X->kind == TK_I64 && key->windows < 16) return ZKDL_EINVAL;
+    int m = 0;
+    while (((uint64_t)1 << m) < X->numel) ++m;
+    if (((uint64_t)1 << m) != X->numel) return ZKDL_EINVAL;
+    const uint64_t cols = (uint64_t)1 << (m / 2), rows = (uint64_t)1 << (m - m / 2);
+    if (cols > key->ncols) return ZKDL_EINVAL;
+    if (*ncommit < rows) {
+        *ncommit = rows;
+        return ZKDL_ESMALL;
+    }
+    for (uint64_t j = 0; blind && j < rows; ++j) {   // blinding scalars are field elements: below r
+        bool below = false;
+        for (int i = 31; i >= 0 && !below; --i) {
+            const uint8_t rb = (uint8_t)(frc::MOD[i >> 2] >> (8 * (i & 3)));
+            if (blind[j].le[i] > rb) return ZKDL_EINVAL;
+            below = blind[j].le[i] < rb;
+        }
+        if (!below) return ZKDL_EINVAL;
+    }
+    ZK_HIP(ctx, hipSetDevice(ctx->device));
+    const uint64_t nchunk = (cols + CK_CHUNK - 1) / CK_CHUNK;
+    G1* part = (G1*)zk_alloc(ctx, sizeof(G1) * rows * nchunk);
+    uint8_t* out_dev = (uint8_t*)zk_alloc(ctx, rows * 96);
+    uint32_t* rho_dev = blind ? (uint32_t*)zk_alloc(ctx, rows * 32) : nullptr;
+    int rc = (part && out_dev && (!blind || rho_dev)) ? ZKDL_OK : ZKDL_ENOMEM;
+    hipError_t e = hipSuccess;
+    if (rc == ZKDL_OK && blind) e = hipMemcpyAsync(rho_dev, blind, rows * 32, hipMemcpyHostToDevice, ctx->stream);
+    if (rc == ZKDL_OK && e == hipSuccess) {
+        const uint64_t nt = rows * nchunk;
+        const unsigned grid = (unsigned)((nt + 63) / 64);
+        // the key's tables have `windows` entries per generator whatever the tensor's width
+        if (X->kind == TK_I32)
+            hipLaunchKernelGGL((k_commit_partial<int32_t>), dim3(grid), dim3(64), 0, ctx->stream, (const int32_t*)X->data, rows,
+                               cols, nchunk, key->windows, key->table, part);
+        else
+            hipLaunchKernelGGL((k_commit_partial<int64_t>), dim3(grid), dim3(64), 0, ctx->stream, (const int64_t*)X->data, rows,
+                               cols, nchunk, key->windows, key->table, part);
+        hipLaunchKernelGGL(k_commit_finish, dim3((unsigned)((rows + 63) / 64)), dim3(64), 0, ctx->stream, part, rows, nchunk,
+                           rho_dev, key->h_table, out_dev);
+        e = hipMemcpyAsync(commitments_out, out_dev, rows * 96, hipMemcpyDeviceToHost, ctx->stream);
+    }
+    hipError_t e2 = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess) e = e2;
+    if (e == hipSuccess) e = hipGetLastError();
+    zk_free(ctx, part);
+    zk_free(ctx, out_dev);
+    zk_free(ctx, rho_dev);
+    if (rc != ZKDL_OK) return rc;
+    ZK_HIP(ctx, e);
+    *ncommit = rows;
+    return ZKDL_OK;
+}

@@ -1,0 +1,101 @@
+"""GPU parity of the commitments: generators, row commitments and openings of the HIP library against the
+Python-integer oracle (oracle/curve.py), byte for byte."""
+import numpy as np
+import pytest
+
+from oracle import curve as EC
+from oracle.field import R_MOD
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def test_generators_match_the_oracle(lib, ctx):
+    say("commit key: generators")
+    key = lib.CommitKey(ctx, b"parity", 16)
+    got = key.generators(0, 17)
+    gens, h = EC.generators(b"parity", 16)
+    assert got == [EC.point_to_bytes(p) for p in gens + [h]]
+    other = lib.CommitKey(ctx, b"", 2)
+    assert other.generators(0, 3) == [EC.point_to_bytes(p) for p in
+                                      EC.generators(b"", 2)[0] + [EC.generators(b"", 2)[1]]]
+
+
+@pytest.mark.parametrize("numel,dtype,blinded", [(1, "i32", True), (2, "i32", False), (64, "i32", True), (256, "i64", True),
+                                                 (2048, "i32", True), (512, "i64", False)])
+def test_row_commitments_match_the_oracle(lib, ctx, numel, dtype, blinded):
+    import torch
+    say(f"hyrax_commit numel={numel} {dtype} blinded={blinded}")
+    rng = np.random.default_rng(numel + 7)
+    if dtype == "i32":
+        vals = rng.integers(-2 ** 31, 2 ** 31, numel, dtype=np.int64).astype(np.int32)
+        edge = [0, -1, 2 ** 31 - 1, -2 ** 31, 1, 16, -16, 255]
+    else:
+        vals = rng.integers(-2 ** 47, 2 ** 47, numel, dtype=np.int64)
+        edge = [0, -1, 2 ** 63 - 1, -2 ** 63, 2 ** 47 - 1, -2 ** 47, 1 << 60, -(1 << 32)]
+    vals[:min(numel, len(edge))] = edge[:min(numel, len(edge))]
+    rows, cols = EC.matrix_shape(numel)
+    key = lib.CommitKey(ctx, b"rows", cols, 64 if dtype == "i64" else 32)
+    blind = [int(v) for v in rng.integers(1, 2 ** 62, rows)] if blinded else None
+    if blinded:
+        blind[0] = R_MOD - 1
+    x = lib.tensor_wrap_int(ctx, torch.from_numpy(vals).cuda())
+    got = lib.hyrax_commit(ctx, key, x, blind)
+    gens, h = EC.generators(b"rows", cols)
+    want = EC.commit_rows([int(v) for v in vals], blind if blinded else [0] * rows, gens, h)
+    assert got == [EC.point_to_bytes(p) for p in want]
+
+
+def test_opening_is_accepted_by_the_oracles_verifier(lib, ctx):
+    import torch
+    say("hyrax_open")
+    rng = np.random.default_rng(3)
+    numel = 128
+    vals = rng.integers(-2 ** 31, 2 ** 31, numel, dtype=np.int64).astype(np.int32)
+    rows, cols = EC.matrix_shape(numel)
+    key = lib.CommitKey(ctx, b"open", cols)
+    blind = [int(v) for v in rng.integers(1, 2 ** 62, rows)]
+    x = lib.tensor_wrap_int(ctx, torch.from_numpy(vals).cuda())
+    coms = [EC.point_from_bytes(c) for c in lib.hyrax_commit(ctx, key, x, blind)]
+    point = [int(v) for v in rng.integers(1, 2 ** 62, 7)]
+    t, rho_star, y = lib.hyrax_open(ctx, x, blind, point)
+    assert (t, rho_star, y) == EC.open_rows([int(v) for v in vals], blind, point)
+    gens, h = EC.generators(b"open", cols)
+    assert EC.verify_opening(coms, point, t, rho_star, y, gens, h)
+
+
+def test_commitments_are_homomorphic(lib, ctx):
+    """Sec. 2.3: the product of two commitments commits to the sum of the tensors."""
+    import torch
+    say("homomorphism")
+    rng = np.random.default_rng(5)
+    a = rng.integers(-2 ** 30, 2 ** 30, 32, dtype=np.int64).astype(np.int32)
+    b = rng.integers(-2 ** 30, 2 ** 30, 32, dtype=np.int64).astype(np.int32)
+    key = lib.CommitKey(ctx, b"hom", 4)
+    ra, rb = [int(v) for v in rng.integers(1, 2 ** 60, 8)], [int(v) for v in rng.integers(1, 2 ** 60, 8)]
+    ca = lib.hyrax_commit(ctx, key, lib.tensor_wrap_int(ctx, torch.from_numpy(a).cuda()), ra)
+    cb = lib.hyrax_commit(ctx, key, lib.tensor_wrap_int(ctx, torch.from_numpy(b).cuda()), rb)
+    cs = lib.hyrax_commit(ctx, key, lib.tensor_wrap_int(ctx, torch.from_numpy(a + b).cuda()), [x + y for x, y in zip(ra, rb)])
+    for u, v, w in zip(ca, cb, cs):
+        assert EC.add(EC.point_from_bytes(u), EC.point_from_bytes(v)) == EC.point_from_bytes(w)
+
+
+def test_commit_rejects_bad_arguments(lib, ctx):
+    import torch
+    key = lib.CommitKey(ctx, b"args", 4)
+    x64 = lib.tensor_wrap_int(ctx, torch.zeros(16, dtype=torch.int64).cuda())
+    with pytest.raises(lib.ZkdlError):
+        lib.hyrax_commit(ctx, key, x64)                      # a 32-bit key
+    big = lib.tensor_wrap_int(ctx, torch.zeros(1024, dtype=torch.int32).cuda())
+    with pytest.raises(lib.ZkdlError):
+        lib.hyrax_commit(ctx, key, big)                      # 32 columns, the key has 4
+    x = lib.tensor_wrap_int(ctx, torch.zeros(16, dtype=torch.int32).cuda())
+    with pytest.raises(lib.ZkdlError):
+        lib.hyrax_commit(ctx, key, x, [R_MOD] * 4)           # blinding not below r
+    with pytest.raises(lib.ZkdlError):
+        lib.CommitKey(ctx, b"x" * 17, 4)
+    with pytest.raises(lib.ZkdlError):
+        lib.CommitKey(ctx, b"x", 3)

@@ -18,7 +18,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b([a-z_0-9]+)\s*\(", header)) - {"defined"}
     declared = {d for d in declared if d.startswith(("zkdl_", "fr_", "mle_", "sumcheck_", "zkrelu_",
-                                                       "aggregate_", "reindex_", "claims_"))}
+                                                       "aggregate_", "reindex_", "claims_", "hyrax_"))}
     assert declared == set(zk.EXPORTED_SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -26,6 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_montgomery_constants_rederive():
     assert zk.selfcheck_constants() == 0
+    assert zk.commit_selfcheck() == 0       # the base field of the commitments
 
 
 def test_host_fr_mul_matches_python_integers():
