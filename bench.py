@@ -265,6 +265,15 @@ def main():
         dw = {k: wit[k] for k in ("L", "B", "width", "T", "Q", "R")}
         for k in ("A", "W", "GZ", "Zr", "GA"):
             dw[k] = torch.from_numpy(np.ascontiguousarray(wit[k])).cuda()
+        # commitments to the window's int32 stacks (Protocol zkdl, the commit line): rows of sqrt(size) entries
+        for nm in ("A", "W"):
+            flat = dw[nm].reshape(-1)
+            mm = flat.numel().bit_length() - 1
+            key = zk.CommitKey(ctx, nm.encode(), 1 << (mm // 2))
+            xv = zk.tensor_wrap_int(ctx, flat)
+            cm_med, _ = timed(lambda: zk.hyrax_commit(ctx, key, xv), 3)
+            out["config"]["commit_ms_%s_stack_2p%d" % (nm, mm)] = 1e3 * cm_med
+            key.close()
         ag_med, ag_min = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + 3)), 5)
         out["config"]["proof_ms_batch64_8layer_step"] = 1e3 * ag_med
         out["config"]["proof_ms_batch64_8layer_step_min"] = 1e3 * ag_min

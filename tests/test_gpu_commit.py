@@ -99,3 +99,36 @@ def test_commit_rejects_bad_arguments(lib, ctx):
         lib.CommitKey(ctx, b"x" * 17, 4)
     with pytest.raises(lib.ZkdlError):
         lib.CommitKey(ctx, b"x", 3)
+
+
+def test_full_size_activation_stack_opens_correctly(lib, ctx):
+    """The activation stack of the 8 x 1024^2, batch-64 window (2^19 int32, 1024 rows of 512 columns): the
+    oracle cannot recompute 2^19 scalar multiplications in seconds, so the commitments are checked through
+    the relation that holds at any size - the oracle's verifier combines the 1024 row commitments at a random
+    point (the homomorphism of Sec. 2.3) and accepts the library's opening - and 16 sampled rows are
+    recomputed from their definition."""
+    import torch
+    from workloads import fcnn_window, CONFIG_SEED
+    say("hyrax_commit on the 2^19 activation stack")
+    wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)
+    vals = np.ascontiguousarray(wit["A"]).reshape(-1)
+    rows, cols = EC.matrix_shape(vals.size)
+    rng = np.random.default_rng(11)
+    blind = [int.from_bytes(rng.bytes(31), "little") for _ in range(rows)]
+    key = lib.CommitKey(ctx, b"A", cols)
+    x = lib.tensor_wrap_int(ctx, torch.from_numpy(vals).cuda())
+    raw = lib.hyrax_commit(ctx, key, x, blind)
+    coms = [EC.point_from_bytes(c) for c in raw]
+    gens = [EC.point_from_bytes(g) for g in key.generators(0, cols)]
+    h = EC.point_from_bytes(key.generators(cols, 1)[0])
+    for i in (0, 1, cols - 1):
+        assert gens[i] == EC.generator(b"A", i)
+    assert h == EC.generator(b"A", EC.H_INDEX)
+    point = [int.from_bytes(rng.bytes(31), "little") for _ in range(19)]
+    t, rho_star, y = lib.hyrax_open(ctx, x, blind, point)
+    say("  oracle: verifying the opening")
+    assert EC.verify_opening(coms, point, t, rho_star, y, gens, h)
+    say("  oracle: sampled rows")
+    for j in (0, 5, rows - 1):
+        row = [int(v) for v in vals[j * cols:(j + 1) * cols]]
+        assert EC.commit(row, blind[j], gens, h) == coms[j]
