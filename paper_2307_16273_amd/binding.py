@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "aggregate_prove_ft", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read", "zkdl_selfbench",
     "zkdl_commit_key_create", "zkdl_commit_key_destroy", "zkdl_commit_key_generators", "hyrax_commit", "hyrax_open",
-    "zkdl_commit_selfcheck",
+    "zkdl_commit_selfcheck", "aggregate_verify", "zkdl_host_aggregate_verify",
 ]
 
 PROF_CLASSES = {"sc_round_fused": 0, "sc_round_first": 1, "partial_eval": 2, "zk_bin": 3, "zk_lin": 4,
@@ -100,6 +100,8 @@ def load_library():
         "zkdl_commit_key_generators": [vp, vp, u64, u64, vp],
         "hyrax_commit": [vp, vp, vp, vp, vp, psz], "hyrax_open": [vp, vp, vp, vp, sz, vp, vp, vp],
         "zkdl_commit_selfcheck": [],
+        "aggregate_verify": [vp, vp, sz, vp, C.POINTER(i), vp, psz, vp, psz],
+        "zkdl_host_aggregate_verify": [vp, sz, vp, C.POINTER(i), vp, psz, vp, psz],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -518,3 +520,31 @@ def hyrax_open(ctx, x, blind, point):
 
 def commit_selfcheck():
     return load_library().zkdl_commit_selfcheck()
+
+
+def aggregate_verify(ctx, proof, tr):
+    """The library's verifier: on the GPU, or (ctx None) the same program on the CPU.  Returns a dict with
+    verdict (0 = accepted), points and claims_left; the transcript advances only if the proof is accepted."""
+    proof = bytes(proof)
+    buf = C.create_string_buffer(proof, len(proof))
+    verdict = C.c_int(-1)
+    pts = C.create_string_buffer(32 * POINTS_CAP)
+    npts = C.c_size_t(POINTS_CAP)
+    claims = (Claim * 16)()
+    ncl = C.c_size_t(16)
+    if ctx is None:
+        _check(load_library().zkdl_host_aggregate_verify(buf, len(proof), tr.handle, C.byref(verdict), pts, C.byref(npts),
+                                                         claims, C.byref(ncl)), "zkdl_host_aggregate_verify")
+    else:
+        _check(load_library().aggregate_verify(ctx.handle, buf, len(proof), tr.handle, C.byref(verdict), pts, C.byref(npts),
+                                               claims, C.byref(ncl)), "aggregate_verify", ctx)
+    out = dict(verdict=verdict.value, points=[], claims_left=[])
+    if verdict.value == 0:
+        out["points"] = _split_fr(pts.raw, npts.value)
+        p = out["points"]
+        out["claims_left"] = [
+            dict(tensor=CLAIM_TENSORS[c.tensor],
+                 point=[x for s in range(c.nseg) for x in p[c.seg_off[s]:c.seg_off[s] + c.seg_len[s]]],
+                 value=int.from_bytes(bytes(c.value), "little"))
+            for c in claims[:ncl.value]]
+    return out

@@ -1550,12 +1550,24 @@ extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_t
     if (rc == ZKDL_OK) rc = enqueue_zkrelu(ctx, w->Zr, w->GA, N * w->B * w->width, (int)w->Q, (int)w->R, 0, nullptr);
     const size_t pend = ctx->proof_len;
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
-    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims_out) {
-        const int ln = ilog2_u64(N), lb = ilog2_u64(w->B), lw = ilog2_u64(w->width);
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims_out)
+        *nclaims = zk_claims_unlinked(claims_out, staged_proof(ctx), w->L, w->B, w->width, w->T, w->Q, w->R, cf, pf, ca, pa,
+                                      cw, pw, cz, pz, pend);
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
+// The 14 claims of an unlinked window from its proof bytes: c* = first challenge index and p* = proof offset of
+// forward, gradA, gradW and zkReLU, pend = end of the proof.
+size_t zk_claims_unlinked(zkdl_claim* claims_out, const uint8_t* proof, uint32_t L, uint32_t B, uint32_t width, uint32_t T,
+                          uint32_t Q, uint32_t R, int cf, size_t pf, int ca, size_t pa, int cw, size_t pw, int cz, size_t pz,
+                          size_t pend) {
+    {
+        const uint64_t N = (uint64_t)L * T;
+        const int ln = ilog2_u64(N), lb = ilog2_u64(B), lw = ilog2_u64(width);
         const int li = ln + lb + lw;
         int lj = 0;
-        while ((1u << lj) < w->Q + w->R) ++lj;
-        ClaimList cl = {claims_out, 0, staged_proof(ctx)};
+        while ((1u << lj) < Q + R) ++lj;
+        ClaimList cl = {claims_out, 0, proof};
         // a family's challenges: w (ln), u0 (l1), u1 (l3), then the rounds v_n (ln), v_i (l2)
         {   // forward: l1 = lb, l2 = lw, l3 = lw
             const int u0 = cf + ln, u1 = u0 + lb, vn = u1 + lw, vi = vn + ln, rounds = ln + lw;
@@ -1582,9 +1594,8 @@ extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_t
         cl.add_at(ZKDL_T_GA, {{cz + 2 * li, li}}, pz + 96);
         cl.add_at(ZKDL_T_GZ_RELU, {{cz + 3 * li, li}}, pz + 128);
         cl.add_at(ZKDL_T_AUX, {{c_vm, 1}, {c_v, li}, {c_vm + 1, lj}}, pend - 64);
-        *nclaims = cl.n;
+        return cl.n;
     }
-    return rc != ZKDL_OK ? rc : rc2;
 }
 
 // The same window with its three matrix-product families in the optimized aggregated form (App. B,

@@ -222,5 +222,8 @@ int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64
               int given_points);
 
 // ---- api.hip -----------------------------------------------------------------------
+size_t zk_claims_unlinked(zkdl_claim* claims_out, const uint8_t* proof, uint32_t L, uint32_t B, uint32_t width, uint32_t T,
+                          uint32_t Q, uint32_t R, int cf, size_t pf, int ca, size_t pa, int cw, size_t pw, int cz, size_t pz,
+                          size_t pend);
 void zk_write_proof_words(zkdl_ctx* ctx, const uint32_t* words, int n);   // appends a header
 void zk_host_absorb_u32(zkdl_transcript* t, const char* label, const uint32_t* words, int n);

@@ -726,6 +726,38 @@ def test_aggregate_ft(lib, ctx, layers, width, batch, steps):
     P.aggregate_ft_verify(got["proof"], OracleTranscript(35))
 
 
+@pytest.mark.parametrize("layers,width,batch,steps,ft", [(2, 8, 4, 2, False), (4, 32, 8, 1, True), (1, 16, 2, 1, False),
+                                                         (8, 16, 4, 16, True)])
+def test_gpu_verifier_agrees_with_the_oracles(lib, ctx, layers, width, batch, steps, ft):
+    """aggregate_verify on the GPU: accepts the library's proof, re-derives the oracle's challenges, ends in the
+    oracle's transcript state, reports the claims the prover reported; refuses tampered proofs with the verdict
+    the same program gives on the CPU, leaving the transcript alone."""
+    say(f"aggregate_verify L={layers} w={width} B={batch} T={steps} ft={ft}")
+    wit = fcnn_window(CONFIG_SEED + 80 + layers, layers, width, batch, steps)
+    tr = lib.Transcript(36)
+    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr, ft=ft)
+    ots = OracleTranscript(36)
+    (P.aggregate_ft_verify if ft else P.aggregate_verify)(got["proof"], ots)
+    tv = lib.Transcript(36)
+    ver = lib.aggregate_verify(ctx, got["proof"], tv)
+    assert ver["verdict"] == 0
+    assert ver["points"] == ots.challenges == got["points"]
+    assert tv.digest() == ots.digest() == tr.digest()
+    if not ft:
+        assert ver["claims_left"] == got["claims_left"]
+    proof = got["proof"]
+    for pos in (5, 29, 40, 100, len(proof) // 3, len(proof) // 2, len(proof) - 200, len(proof) - 1):
+        bad = bytearray(proof)
+        bad[pos] ^= 0x10
+        t1, t2 = lib.Transcript(36), lib.Transcript(36)
+        before = t1.digest()
+        on_gpu = lib.aggregate_verify(ctx, bytes(bad), t1)
+        on_cpu = lib.aggregate_verify(None, bytes(bad), t2)
+        assert on_gpu["verdict"] != 0 and on_gpu["verdict"] == on_cpu["verdict"]
+        assert t1.digest() == before
+    assert lib.aggregate_verify(ctx, proof, lib.Transcript(37))["verdict"] != 0     # another transcript
+
+
 @pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 32, 8, 1), (1, 16, 2, 1), (2, 4, 2, 4),
                                                       (4, 16, 8, 4)])
 def test_aggregate_linked(lib, ctx, layers, width, batch, steps):
@@ -968,6 +1000,8 @@ def test_large_aggregates_by_properties(lib, ctx, name, layers, width, batch, st
     assert tr.digest() == ots.digest()
     assert got["points"] == ots.challenges
     assert got["claims_left"] == expected_claims_unlinked(res, (layers * steps).bit_length() - 1)
+    ver = lib.aggregate_verify(ctx, got["proof"], lib.Transcript(CONFIG_SEED + cfg))
+    assert ver["verdict"] == 0 and ver["points"] == ots.challenges and ver["claims_left"] == got["claims_left"]
     ctx.trim()
     # the same window with the claims chained: every link holds, and the one claim left on each of
     # A, G_Z and W (the merge on W runs over the whole stack, 2^26 or 2^27 elements) is the MLE of

@@ -4,6 +4,7 @@ import os
 import re
 
 import numpy as np
+import pytest
 
 import paper_2307_16273_amd as zk
 from oracle.field import R_MOD
@@ -53,3 +54,59 @@ def test_host_transcript_matches_oracle_format():
             assert a.digest() == b.digest()
             assert a.challenge() == b.challenge()
             assert a.digest() == b.digest()
+
+
+def _host_transcript(seed):
+    return zk.Transcript(seed)
+
+
+def test_host_verifier_accepts_the_oracles_proofs_and_rejects_tampering():
+    """The library's verifier (the program that also runs on the GPU), compiled for the host: it accepts the
+    oracle's proofs of both forms, ends in the oracle's transcript state with the oracle's challenges,
+    reports the claims the oracle's verifier returns, and refuses every flipped byte as the oracle does."""
+    from oracle import protocols as P
+    from workloads import fcnn_window, CONFIG_SEED
+    for shape in ((2, 8, 4, 2), (1, 4, 2, 1), (4, 4, 2, 1)):
+        wit = fcnn_window(CONFIG_SEED + 130, *shape)
+        for ft in (False, True):
+            ots = OracleTranscript(9)
+            buf, _ = (P.aggregate_ft_prove if ft else P.aggregate_prove)(wit, ots)
+            tr = _host_transcript(9)
+            got = zk.aggregate_verify(None, buf, tr)
+            assert got["verdict"] == 0
+            assert got["points"] == ots.challenges
+            assert tr.digest() == ots.digest()
+            if not ft:
+                res = P.aggregate_verify(buf, OracleTranscript(9))
+                n = shape[0] * shape[3]
+                names = {"fwd": ("Z", "A", "W"), "gradA": ("GA", "GZ_NEXT", "W_NEXT"), "gradW": ("GW", "A", "GZ")}
+                k = 0
+                for fam in ("fwd", "gradA", "gradW"):
+                    proof, _ = res[fam]
+                    assert got["claims_left"][k]["tensor"] == names[fam][0] and got["claims_left"][k]["value"] == proof.claim0
+                    assert [c["value"] for c in got["claims_left"][k + 1:k + 3]] == proof.finals[1:]
+                    k += 3
+                assert [c["value"] for c in got["claims_left"][9:13]] == res["zkrelu"]["c_in"]
+                assert got["claims_left"][13]["point"] == res["zkrelu"]["aux_claim"]["point"]
+                assert got["claims_left"][13]["value"] == res["zkrelu"]["aux_claim"]["value"]
+            # tampering: the library refuses a flip of ANY byte and leaves the transcript alone; where the byte
+            # belongs to a field element (sampled; the oracle's parser is not hardened against broken size
+            # words) the oracle's verifier refuses it as well
+            for pos in range(len(buf)):
+                bad = bytearray(buf)
+                bad[pos] ^= 0x04
+                tr2 = _host_transcript(9)
+                before = tr2.digest()
+                assert zk.aggregate_verify(None, bytes(bad), tr2)["verdict"] != 0, pos
+                assert tr2.digest() == before
+            first_element = 32 + (16 if not ft else 16)
+            for pos in (first_element + 5, first_element + 32 + 7, len(buf) // 2 + 40, len(buf) - 70, len(buf) - 3):
+                bad = bytearray(buf)
+                bad[pos] ^= 0x04
+                with pytest.raises(AssertionError):
+                    (P.aggregate_ft_verify if ft else P.aggregate_verify)(bytes(bad), OracleTranscript(9))
+            # a proof on the wrong transcript is refused too
+            assert zk.aggregate_verify(None, buf, _host_transcript(10))["verdict"] != 0
+            # truncated and extended proofs
+            assert zk.aggregate_verify(None, buf[:-1], _host_transcript(9))["verdict"] != 0
+            assert zk.aggregate_verify(None, buf + b"\x00", _host_transcript(9))["verdict"] != 0
