@@ -195,6 +195,108 @@ def matmul_ft_verify(buf, n, d1, d2, d3, ts):
 
 
 # --------------------------------------------------------------------------
+# batched matrix product, general aggregated form (Sec. 4, Eq. tensor-op-aggr; App. B, Protocol
+# tensor-op-aggr): the output Y is a (committed) input of the sumcheck, not a claim
+# --------------------------------------------------------------------------
+GA_MAGIC = 0x41474B5A   # "ZKGA"
+
+
+def matmul_general_prove(x0, shape0, x1, shape1, y, ts):
+    """N instances Y[n] = X0[n] X1[n] proved from the three stacks themselves:
+      0 = sum_n sum_i sum_j beta~(w, n) beta~(u, i) (D_in^{-1} Y(n, i) - X0(n, i0, j) X1(n, j, i1)),
+    i = (i0, i1) the output index (D_out = D1 D3 values), j the inner index (D_in = D2), w over the stack
+    and u over the output index drawn by the verifier (Eq. tensor-op-aggr with f(a, b) = a b).
+    Stack rounds t = 0..log N - 1 (Protocol tensor-op-aggr): the prover sends f_t at x = 0, 1, 2, the
+    round polynomial without the factor beta~(w_t, x) and with beta~(w_[t+1:], n') over the unbound stack
+    variables; the verifier checks (1 - w_t) f_t(0) + w_t f_t(1) = claim (0 for t = 0, f_{t-1}(v_{t-1})
+    after).  Then the textbook sumcheck of Eq. tensor-op-compressed over (i0, i1, j), in that order,
+    degree 2, whose claim_0 = f_{n-1}(v_{n-1}) the transcript already fixes (not absorbed).
+    Finals: Y~(v_n, v_i0, v_i1), X0~(v_n, v_i0, v_j), X1~(v_n, v_j, v_i1); beta~(u, v_i) is the verifier's.
+    Transcript: header "tensor_op_aggr" (N, D1, D2, D3); one draw (w, u); per stack round "f" (three
+    evaluations) and a draw; the inner rounds and finals.  Proof: "ZKGA", log N, log D1, log D3, log D2,
+    0, 0, 0; log N x 3 evaluations; one SC block (3 finals, degree 2)."""
+    n, d1, d2 = shape0
+    n_, d2_, d3 = shape1
+    assert n == n_ and d2 == d2_
+    ln, l1, l2, l3 = ilog2(n), ilog2(d1), ilog2(d2), ilog2(d3)
+    ts.absorb_u32(b"tensor_op_aggr", [n, d1, d2, d3])
+    pt = ts.challenges_vec(ln + l1 + l3)
+    w, u = pt[:ln], pt[ln:]
+    m = d1 * d3 * d2
+    a = np.asarray(x0, dtype=object).reshape(n, d1, 1, d2)
+    b = np.transpose(np.asarray(x1, dtype=object).reshape(n, d2, d3), (0, 2, 1)).reshape(n, 1, d3, d2)
+    yy = np.asarray(y, dtype=object).reshape(n, d1, d3, 1)
+    ones = np.ones((n, d1, d3, d2), dtype=object)
+    cur_y = (yy * ones).reshape(n, m) % R_MOD           # every table over (n; i0, i1, j), broadcast written out
+    cur_0 = (a * ones).reshape(n, m) % R_MOD
+    cur_1 = (b * ones).reshape(n, m) % R_MOD
+    bu = np.repeat(beta_table(u), d2)                   # beta~(u, (i0, i1)), every j
+    dinv = pow(d2, -1, R_MOD)
+
+    def weighted(ty, t0, t1, bs):
+        tot = 0
+        for row in range(ty.shape[0]):
+            tot += int(bs[row]) * int(np.sum(bu * (dinv * ty[row] - t0[row] * t1[row])) % R_MOD)
+        return tot % R_MOD
+    claim = 0
+    assert weighted(cur_y, cur_0, cur_1, beta_table(w)) == 0, "Y is not the product of X0 and X1"
+    stack_rounds, vs = [], []
+    for t in range(ln):
+        half = cur_y.shape[0] // 2
+        bs = beta_table(w[t + 1:])
+        f = []
+        for x in range(3):
+            at = [(c[:half] + x * (c[half:] - c[:half])) % R_MOD for c in (cur_y, cur_0, cur_1)]
+            f.append(weighted(at[0], at[1], at[2], bs))
+        assert ((1 - w[t]) * f[0] + w[t] * f[1]) % R_MOD == claim, "stack round invariant broken"
+        ts.absorb_fr(b"f", f)
+        v = ts.challenge()
+        cur_y, cur_0, cur_1 = [(c[:half] + v * (c[half:] - c[:half])) % R_MOD for c in (cur_y, cur_0, cur_1)]
+        claim = _lagrange(f, v)
+        stack_rounds.append(f)
+        vs.append(v)
+    inner, vi = prove([bu, cur_y.reshape(-1), cur_0.reshape(-1), cur_1.reshape(-1)],
+                      [(dinv, [0, 1]), (R_MOD - 1, [0, 2, 3])], 2, ts, absorb_claim=False,
+                      report=lambda f: [f[1], f[2], f[3]])
+    assert inner.claim0 == claim, "the compressed sumcheck does not start at f_{n-1}(v_{n-1})"
+    out = [struct.pack("<IIIIIIII", GA_MAGIC, ln, l1, l3, l2, 0, 0, 0)]
+    for f in stack_rounds:
+        out.extend(to_le(x) for x in f)
+    out.append(inner.to_bytes())
+    info = dict(w=w, u=u, v=vs + vi, stack_rounds=stack_rounds, inner=inner)
+    return b"".join(out), info
+
+
+def matmul_general_verify(buf, n, d1, d2, d3, ts):
+    """Replays the general aggregated protocol; returns (finals (Y~, X0~, X1~), points).  The caller checks
+    the finals against the (committed) stacks: Y~ at (v_n, v_i0, v_i1), X0~ at (v_n, v_i0, v_j), X1~ at
+    (v_n, v_j, v_i1)."""
+    magic, ln, l1, l3, l2, z0, z1, z2 = struct.unpack_from("<IIIIIIII", buf, 0)
+    assert magic == GA_MAGIC and (ln, l1, l3, l2) == (ilog2(n), ilog2(d1), ilog2(d3), ilog2(d2))
+    assert z0 == z1 == z2 == 0
+    ts.absorb_u32(b"tensor_op_aggr", [n, d1, d2, d3])
+    pt = ts.challenges_vec(ln + l1 + l3)
+    w, u = pt[:ln], pt[ln:]
+    off = 32
+    claim, vs = 0, []
+    for t in range(ln):
+        f = [from_le(buf[off + 32 * x:off + 32 * x + 32]) for x in range(3)]
+        off += 96
+        assert ((1 - w[t]) * f[0] + w[t] * f[1]) % R_MOD == claim, "g(0)+g(1) != claim"
+        ts.absorb_fr(b"f", f)
+        v = ts.challenge()
+        claim = _lagrange(f, v)
+        vs.append(v)
+    inner, end = SumcheckProof.from_bytes(buf, off)
+    assert end == len(buf) and inner.n_finals == 3 and inner.degree == 2 and len(inner.rounds) == l1 + l3 + l2
+    last, vi = verify_rounds(inner, ts, absorb_claim=False, expected_claim0=claim)
+    yf, f0, f1 = inner.finals
+    dinv = pow(d2, -1, R_MOD)
+    assert beta_point(u, vi[:l1 + l3]) * (dinv * yf - f0 * f1) % R_MOD == last, "final claim mismatch"
+    return inner.finals, dict(w=w, u=u, v=vs + vi)
+
+
+# --------------------------------------------------------------------------
 # re-indexing of stacked tensors (Sec. 4, Eq. sc-reindex; Protocol zkdl, the re-indexing line)
 # --------------------------------------------------------------------------
 RI_MAGIC = 0x49524B5A   # "ZKRI"

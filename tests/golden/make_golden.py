@@ -115,6 +115,20 @@ def aggregate_ft_case():
             "digest_hex": ts.digest().hex()}
 
 
+def matmul_general_case():
+    """The same product in the general aggregated form (Eq. tensor-op-aggr, Protocol tensor-op-aggr)."""
+    rng = np.random.default_rng(20230717)
+    x0 = rng.integers(-50, 50, (2, 2, 4)).astype(np.int64)
+    x1 = rng.integers(-50, 50, (2, 4, 2)).astype(np.int64)
+    y = np.einsum("nij,njk->nik", x0, x1)
+    ts = Transcript(17)
+    buf, info = P.matmul_general_prove(fr_array(x0), [2, 2, 4], fr_array(x1), [2, 4, 2], fr_array(y), ts)
+    return {"protocol": "sumcheck_matmul_general", "cite": "Eq. tensor-op-aggr, App. B Protocol tensor-op-aggr", "seed": 17,
+            "x0": x0.reshape(-1).tolist(), "x0_shape": [2, 2, 4], "x1": x1.reshape(-1).tolist(), "x1_shape": [2, 4, 2],
+            "y": y.reshape(-1).tolist(),
+            "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
+
+
 def reindex_case():
     """Re-indexing sumcheck (Eq. sc-reindex): stack of N = 4 tensors of D = 8, two sub-stacks."""
     rng = np.random.default_rng(20230718)
@@ -156,7 +170,7 @@ def stack_merge_case():
 
 if __name__ == "__main__":
     for name, fn in (("product_k3_d3", product_case), ("matmul_n2_2x4x2", matmul_case),
-                     ("matmul_ft_n2_2x4x2", matmul_ft_case),
+                     ("matmul_ft_n2_2x4x2", matmul_ft_case), ("matmul_general_n2_2x4x2", matmul_general_case),
                      ("zkrelu_d4_q5_r3", zkrelu_case), ("zkrelu_at_d4_q5_r3", zkrelu_at_case),
                      ("aggregate_l2_w4_b2_t2", aggregate_case),
                      ("aggregate_linked_l2_w4_b2_t2", aggregate_linked_case),

@@ -28,6 +28,9 @@ def oracle_run(g):
         buf = P.matmul_prove(fr_array(np.array(g["x0"])), g["x0_shape"], fr_array(np.array(g["x1"])), g["x1_shape"], ts)[0]
     elif g["protocol"] == "sumcheck_matmul_ft":
         buf = P.matmul_ft_prove(fr_array(np.array(g["x0"])), g["x0_shape"], fr_array(np.array(g["x1"])), g["x1_shape"], ts)[0]
+    elif g["protocol"] == "sumcheck_matmul_general":
+        buf = P.matmul_general_prove(fr_array(np.array(g["x0"])), g["x0_shape"], fr_array(np.array(g["x1"])), g["x1_shape"],
+                                     fr_array(np.array(g["y"])), ts)[0]
     elif g["protocol"] == "zkrelu_prove":
         buf = P.zkrelu_prove(g["Z"], g["GA"], g["Q"], g["R"], ts)[0]
     elif g["protocol"] == "zkrelu_prove_at":
@@ -64,7 +67,7 @@ def _without_repeats(points, drawn):
     return out
 
 
-NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "zkrelu_d4_q5_r3", "zkrelu_at_d4_q5_r3", "aggregate_l2_w4_b2_t2",
+NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "matmul_general_n2_2x4x2", "zkrelu_d4_q5_r3", "zkrelu_at_d4_q5_r3", "aggregate_l2_w4_b2_t2",
          "aggregate_linked_l2_w4_b2_t2", "aggregate_ft_l2_w4_b2_t2", "merge_d4_k3", "stack_merge_n4_d8_k2",
          "reindex_n4_d8_k2"]
 
@@ -93,6 +96,11 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
         x0 = lib.fr_tensor_upload(ctx, np.array(g["x0"], dtype=np.int64), tuple(g["x0_shape"]))
         x1 = lib.fr_tensor_upload(ctx, np.array(g["x1"], dtype=np.int64), tuple(g["x1_shape"]))
         got = getattr(lib, g["protocol"])(ctx, x0, x1, tr)
+    elif g["protocol"] == "sumcheck_matmul_general":
+        x0 = lib.fr_tensor_upload(ctx, np.array(g["x0"], dtype=np.int64), tuple(g["x0_shape"]))
+        x1 = lib.fr_tensor_upload(ctx, np.array(g["x1"], dtype=np.int64), tuple(g["x1_shape"]))
+        yy = lib.fr_tensor_upload(ctx, np.array(g["y"], dtype=np.int64), (g["x0_shape"][0], g["x0_shape"][1], g["x1_shape"][2]))
+        got = lib.sumcheck_matmul_general(ctx, x0, x1, yy, tr)
     elif g["protocol"] == "reindex_prove":
         n, d = g["x_shape"]
         x = lib.fr_tensor_upload(ctx, np.array(g["x"], dtype=np.int64), (n, d))

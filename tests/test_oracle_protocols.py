@@ -365,3 +365,62 @@ def test_stack_merge_verifier_rejects_tampering_and_wrong_points():
             other[1][which] = (other[1][which] + 1) % R_MOD
             with pytest.raises(AssertionError):
                 P.stack_merge_verify(b2, n, d, other, Transcript(18), bind_statement=bind)
+
+
+# --------------------------------------------------------------------------
+# general aggregated form (Eq. tensor-op-aggr, Protocol tensor-op-aggr)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("n,d1,d2,d3", [(4, 2, 4, 2), (1, 2, 2, 4), (2, 1, 8, 1), (8, 2, 1, 2), (1, 1, 1, 1)])
+def test_matmul_general_form(n, d1, d2, d3):
+    """Honest stacks: the verifier accepts, the finals are the MLEs of Y, X0, X1 at the challenge point, and
+    every f_t(x) equals the triple sum of Protocol tensor-op-aggr written out with MLE evaluations."""
+    rng = np.random.default_rng(1000 * n + 10 * d2 + d3)
+    x0 = rng.integers(-50, 50, (n, d1, d2)).astype(object)
+    x1 = rng.integers(-50, 50, (n, d2, d3)).astype(object)
+    y = np.einsum("nij,njk->nik", x0, x1)
+    ts = Transcript(41)
+    buf, info = P.matmul_general_prove(fr_array(x0), [n, d1, d2], fr_array(x1), [n, d2, d3], fr_array(y), ts)
+    tv = Transcript(41)
+    finals, pts = P.matmul_general_verify(buf, n, d1, d2, d3, tv)
+    assert tv.digest() == ts.digest() and pts["v"] == info["v"]
+    ln, l1, l2, l3 = (k.bit_length() - 1 for k in (n, d1, d2, d3))
+    v = info["v"]
+    vn, vi0, vi1, vj = v[:ln], v[ln:ln + l1], v[ln + l1:ln + l1 + l3], v[ln + l1 + l3:]
+    assert finals[0] == mle_eval(fr_array(y), vn + vi0 + vi1)
+    assert finals[1] == mle_eval(fr_array(x0), vn + vi0 + vj)
+    assert finals[2] == mle_eval(fr_array(x1), vn + vj + vi1)
+    # f_t(x) from the definition: sum over n', i, j of beta~(w_[t+1:], n') beta~(u, i) (Y/D_in - X0 X1) at (v_<t, x, n')
+    dinv = pow(d2, -1, R_MOD)
+    bu = beta_table(info["u"])
+    for t in range(ln):
+        bs = beta_table(info["w"][t + 1:])
+        for x in range(3):
+            tot = 0
+            for np_ in range(1 << (ln - t - 1)):
+                pn = v[:t] + [x] + P.index_bits(np_, ln - t - 1)
+                for i in range(d1 * d3):
+                    i0, i1 = divmod(i, d3)
+                    bi0, bi1 = P.index_bits(i0, l1), P.index_bits(i1, l3)
+                    acc = mle_eval(fr_array(y), pn + bi0 + bi1)
+                    for j in range(d2):
+                        bj = P.index_bits(j, l2)
+                        acc -= mle_eval(fr_array(x0), pn + bi0 + bj) * mle_eval(fr_array(x1), pn + bj + bi1)
+                    tot += int(bs[np_]) * int(bu[i]) * acc
+            assert info["stack_rounds"][t][x] == tot % R_MOD, (t, x)
+    del dinv
+    # tampering
+    for pos in (36, len(buf) // 2, len(buf) - 4):
+        bad = bytearray(buf)
+        bad[pos] ^= 1
+        with pytest.raises(AssertionError):
+            P.matmul_general_verify(bytes(bad), n, d1, d2, d3, Transcript(41))
+
+
+def test_matmul_general_form_refuses_a_wrong_product():
+    rng = np.random.default_rng(77)
+    x0 = rng.integers(-9, 9, (2, 2, 4)).astype(object)
+    x1 = rng.integers(-9, 9, (2, 4, 2)).astype(object)
+    y = np.einsum("nij,njk->nik", x0, x1)
+    y[1, 0, 1] += 1
+    with pytest.raises(AssertionError):
+        P.matmul_general_prove(fr_array(x0), [2, 2, 4], fr_array(x1), [2, 4, 2], fr_array(y), Transcript(1))
