@@ -60,7 +60,7 @@
  *              finals aux~(k*,v,w*), E~(k*,w*))
  *   aggregate: "ZKAG", L, B, width, T', Q, R, 0, SC block forward, SC block
  *              gradA, SC block gradW, zkReLU proof
- *   "ZKSF" (sumcheck_matmul_ft), "ZKRI" (reindex_prove), "ZKMG"
+ *   "ZKGA" (sumcheck_matmul_general), "ZKSF" (sumcheck_matmul_ft), "ZKRI" (reindex_prove), "ZKMG"
  *   (claims_merge_prove), "ZKMS" (claims_merge_stack_prove) and "ZKAL"
  *   (aggregate_prove_linked) are laid out at their declarations below.
  * points_out also repeats, in front of the draws they precede, points that a
@@ -206,6 +206,29 @@ int sumcheck_matmul(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1,
 int sumcheck_matmul_ft(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1, int transpose_x0,
                        int transpose_x1, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
                        zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints);
+
+/* sumcheck_matmul_general: N products Y[n] = X0[n] X1[n] proved from the three stacks
+ * themselves, in the general aggregated form (Sec. 4, Eq. tensor-op-aggr with f(a, b) = a b;
+ * Protocol tensor-op-aggr):
+ *   0 = sum_n sum_i sum_j beta~(w,n) beta~(u,i) (D2^-1 Y(n,i) - X0(n,i0,j) X1(n,j,i1)),
+ * i = (i0, i1) the output index, j the inner index; w (log N) and u = (u0, u1) (log D1 + log D3)
+ * are drawn.  log N stack rounds with f_t(0), f_t(1), f_t(2), the round polynomial without its
+ * factor beta~(w_t, .): (1 - w_t) f_t(0) + w_t f_t(1) = claim (0 at first), next claim f_t(v_t).
+ * Then the sumcheck of Eq. tensor-op-compressed over (i0, i1, j) in that order, degree 2, whose
+ * claim_0 = f_{n-1}(v_{n-1}) (0 without stack rounds) the transcript already fixes.  The verifier
+ * ends with beta~(u, v_i) (D2^-1 Y~ - X0~ X1~) = last claim.
+ * X0 [N, D1, D2], X1 [N, D2, D3], Y [N, D1, D3], stored as given (no transposes), any kind;
+ * D1, D2, D3 <= 2^16 (ZKDL_ETOOBIG), N <= 2^13.  A Y that is not the product gives a proof the
+ * verifier rejects: the prover does not check it.
+ * claims (host, 3, may be NULL): Y~(v_n, v_i0, v_i1), X0~(v_n, v_i0, v_j), X1~(v_n, v_j, v_i1).
+ * points_out: w, u0, u1, v_n, v_i0, v_i1, v_j (2 log N + 2 log D1 + 2 log D3 + log D2 elements).
+ * Transcript: header "tensor_op_aggr" (N, D1, D2, D3), one draw (w, u), per stack round "f"
+ * (three evaluations) and a draw, then the rounds ("g") and the finals ("f") of the SC block.
+ * Proof: "ZKGA", log2 N, log2 D1, log2 D3, log2 D2, 0, 0, 0; log2 N x 3 evaluations; one SC block
+ * (3 finals, degree 2, log2 D1 + log2 D3 + log2 D2 rounds). */
+int sumcheck_matmul_general(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1, const zkdl_tensor* Y,
+                            zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* claims,
+                            zkdl_fr* points_out, size_t* npoints);
 
 /* sumcheck_hadamard: Eq. exm-hadamard-batched over the whole stack,
  *   Y~(p) = sum_b beta~(p,b) X0(b) X1(b),  p drawn over all log2(numel) variables.

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "zkdl_transcript_challenge", "zkdl_transcript_digest",
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
-    "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_hadamard",
+    "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_matmul_general", "sumcheck_hadamard",
     "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "aggregate_prove_ft", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read", "zkdl_selfbench",
     "zkdl_commit_key_create", "zkdl_commit_key_destroy", "zkdl_commit_key_generators", "hyrax_commit", "hyrax_open",
@@ -83,6 +83,7 @@ def load_library():
         "sumcheck_product_noalloc": [vp, pp, i, vp, vp, psz, vp, vp, psz],
         "sumcheck_matmul": [vp, vp, vp, i, i, vp, vp, psz, vp, vp, psz],
         "sumcheck_matmul_ft": [vp, vp, vp, i, i, vp, vp, psz, vp, vp, psz],
+        "sumcheck_matmul_general": [vp, vp, vp, vp, vp, vp, psz, vp, vp, psz],
         "sumcheck_hadamard": [vp, vp, vp, vp, vp, psz, vp, vp, psz],
         "reindex_prove": [vp, vp, i, pp, C.POINTER(u64), pp, vp, vp, vp, psz, vp, vp, psz],
         "claims_merge_prove": [vp, vp, i, pp, vp, vp, psz, vp, vp, psz],
@@ -349,6 +350,15 @@ def sumcheck_matmul_ft(ctx, x0, x1, tr, transpose_x0=False, transpose_x1=False):
     _check(load_library().sumcheck_matmul_ft(ctx.handle, x0.handle, x1.handle, int(transpose_x0),
                                              int(transpose_x1), tr.handle, o.proof, C.byref(o.proof_len),
                                              o.claims, o.points, C.byref(o.npoints)), "sumcheck_matmul_ft", ctx)
+    return o.result()
+
+
+def sumcheck_matmul_general(ctx, x0, x1, y, tr):
+    """claims: Y~, X0~, X1~ at the final points (the general aggregated form takes Y as a stack)."""
+    o = _Outputs(3)
+    _check(load_library().sumcheck_matmul_general(ctx.handle, x0.handle, x1.handle, y.handle, tr.handle, o.proof,
+                                                  C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
+           "sumcheck_matmul_general", ctx)
     return o.result()
 
 

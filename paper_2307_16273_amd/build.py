@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libzkdl.so")
-SOURCES = ["api.hip", "k_basic.hip", "k_sumcheck.hip", "k_zkrelu.hip", "k_reindex.hip", "k_selfbench.hip", "k_commit.hip", "k_verify.hip"]
+SOURCES = ["api.hip", "k_basic.hip", "k_sumcheck.hip", "k_zkrelu.hip", "k_reindex.hip", "k_selfbench.hip", "k_commit.hip", "k_verify.hip", "k_general.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-unknown-attributes"]
@@ -22,7 +22,7 @@ def _compile(src):
 
 def build(verbose=True):
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         results = list(ex.map(_compile, SOURCES))
     objs = []
     for src, obj, r in results:

@@ -948,6 +948,26 @@ extern "C" int sumcheck_matmul_ft(zkdl_ctx* ctx, const zkdl_tensor* X0, const zk
     return rc != ZKDL_OK ? rc : rc2;
 }
 
+extern "C" int sumcheck_matmul_general(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1,
+                                       const zkdl_tensor* Y, zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
+                                       zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {
+    if (!ctx || !X0 || !X1 || !Y || !tr) return ZKDL_EINVAL;
+    if (X0->ndim != 3 || X1->ndim != 3 || Y->ndim != 3) return ZKDL_EINVAL;
+    const uint64_t N = X0->shape[0], D1 = X0->shape[1], D2 = X0->shape[2], D3 = X1->shape[2];
+    if (X1->shape[0] != N || X1->shape[1] != D2 || Y->shape[0] != N || Y->shape[1] != D1 || Y->shape[2] != D3)
+        return ZKDL_EINVAL;
+    // the rounds over i0, i1 and j run in one block each
+    if (D1 > ((uint64_t)1 << 16) || D2 > ((uint64_t)1 << 16) || D3 > ((uint64_t)1 << 16)) return ZKDL_ETOOBIG;
+    int rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    rc = zk_matmul_general(ctx, X0, X1, Y, ilog2_u64(N), ilog2_u64(D1), ilog2_u64(D2), ilog2_u64(D3), 0);
+    zkdl_fr tmp[3];
+    int ids[3] = {0, 1, 2};
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, ids, 3, tmp);
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims) memcpy(claims, tmp, sizeof(tmp));
+    return rc != ZKDL_OK ? rc : rc2;
+}
+
 extern "C" int sumcheck_hadamard(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1,
                                  zkdl_transcript* tr, uint8_t* proof, size_t* proof_len,
                                  zkdl_fr* claims, zkdl_fr* points_out, size_t* npoints) {

@@ -221,6 +221,12 @@ int zk_matmul_ft(zkdl_ctx* ctx, const FrTab* src, void* work_mem, int ln, int l2
 int zk_zkrelu(zkdl_ctx* ctx, const int64_t* z_dev, const int64_t* ga_dev, uint64_t D, int Q, int R,
               int given_points);
 
+// ---- k_general.hip -----------------------------------------------------------------
+// the batched matrix product in the general aggregated form: header frame, draw of (w, u), the "ZKGA"
+// block; finals Y~, X0~, X1~ -> scal[scal_base ..), scal[scal_base + 3] is used as well
+int zk_matmul_general(zkdl_ctx* ctx, const zkdl_tensor* X0, const zkdl_tensor* X1, const zkdl_tensor* Y, int ln,
+                      int l1, int l2, int l3, int scal_base);
+
 // ---- api.hip -----------------------------------------------------------------------
 size_t zk_claims_unlinked(zkdl_claim* claims_out, const uint8_t* proof, uint32_t L, uint32_t B, uint32_t width, uint32_t T,
                           uint32_t Q, uint32_t R, int cf, size_t pf, int ca, size_t pa, int cw, size_t pw, int cz, size_t pz,

@@ -184,6 +184,78 @@ def test_sumcheck_matmul_ft(lib, ctx, n, d1, d2, d3, t0, t1, kind):
     P.matmul_ft_verify(got["proof"], n, d1, d2, d3, OracleTranscript(6))
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("n,d1,d2,d3,kind", [
+    (2, 2, 4, 2, "fr"),
+    (1, 1, 1, 1, "fr"),            # no round at all: header, claim_0 = 0, the finals
+    (1, 4, 8, 2, "int"),           # no stack rounds: claim_0 = 0
+    (4, 1, 8, 4, "fr"),            # no rounds over i0
+    (4, 8, 4, 1, "int"),           # no rounds over i1
+    (4, 4, 1, 2, "int"),           # no rounds over j
+    (8, 16, 32, 8, "int"),
+    (16, 4, 64, 16, "fr"),
+    (64, 8, 8, 8, "int"),          # six stack rounds
+    (2, 2, 1024, 2, "int"),        # tables of the j rounds longer than a block
+])
+def test_sumcheck_matmul_general(lib, ctx, n, d1, d2, d3, kind):
+    """The general aggregated form on the three stacks: proof bytes, challenges, finals and transcript
+    against the oracle, whose verifier also accepts the library's proof."""
+    import torch
+    say(f"sumcheck_matmul_general N={n} D=({d1},{d2},{d3}) {kind}")
+    rng = np.random.default_rng(n * 1000 + d1 * 100 + d2 * 10 + d3)
+    x0 = rng.integers(-2 ** 15, 2 ** 15, (n, d1, d2), dtype=np.int64)
+    x1 = rng.integers(-2 ** 15, 2 ** 15, (n, d2, d3), dtype=np.int64)
+    y = np.einsum("nij,njk->nik", x0, x1)
+    if kind == "int":
+        a = lib.tensor_wrap_int(ctx, torch.from_numpy(x0.astype(np.int32)).cuda())
+        b = lib.tensor_wrap_int(ctx, torch.from_numpy(x1.astype(np.int32)).cuda())
+        c = lib.tensor_wrap_int(ctx, torch.from_numpy(y).cuda())
+    else:
+        a = lib.fr_tensor_upload(ctx, x0, x0.shape)
+        b = lib.fr_tensor_upload(ctx, x1, x1.shape)
+        c = lib.fr_tensor_upload(ctx, y, y.shape)
+    tr = lib.Transcript(8)
+    got = lib.sumcheck_matmul_general(ctx, a, b, c, tr)
+    ots = OracleTranscript(8)
+    buf, info = P.matmul_general_prove(fr_array(x0), [n, d1, d2], fr_array(x1), [n, d2, d3], fr_array(y), ots)
+    assert got["proof"] == buf
+    assert got["points"] == ots.challenges
+    assert got["claims"] == info["inner"].finals
+    assert tr.digest() == ots.digest()
+    finals, _ = P.matmul_general_verify(got["proof"], n, d1, d2, d3, OracleTranscript(8))
+    assert finals == got["claims"]
+
+
+@pytest.mark.gpu
+def test_sumcheck_matmul_general_wrong_product_is_rejected(lib, ctx):
+    """The prover does not check Y: with one entry of Y off by one the proof it writes fails the
+    oracle's verifier."""
+    say("sumcheck_matmul_general with a wrong Y")
+    n, d1, d2, d3 = 4, 4, 8, 2
+    rng = np.random.default_rng(77)
+    x0 = rng.integers(-2 ** 15, 2 ** 15, (n, d1, d2), dtype=np.int64)
+    x1 = rng.integers(-2 ** 15, 2 ** 15, (n, d2, d3), dtype=np.int64)
+    y = np.einsum("nij,njk->nik", x0, x1)
+    y[2, 1, 1] += 1
+    a, b, c = [lib.fr_tensor_upload(ctx, t, t.shape) for t in (x0, x1, y)]
+    got = lib.sumcheck_matmul_general(ctx, a, b, c, lib.Transcript(8))
+    with pytest.raises(AssertionError):
+        P.matmul_general_verify(got["proof"], n, d1, d2, d3, OracleTranscript(8))
+
+
+@pytest.mark.gpu
+def test_sumcheck_matmul_general_rejects_bad_shapes(lib, ctx):
+    say("sumcheck_matmul_general argument checks")
+    z = lambda *sh: lib.fr_tensor_upload(ctx, np.zeros(sh, dtype=np.int64), sh)
+    for sh0, sh1, shy in [((2, 2, 4), (2, 2, 2), (2, 2, 2)), ((2, 2, 4), (4, 4, 2), (2, 2, 2)),
+                          ((2, 2, 4), (2, 4, 2), (2, 2, 4)), ((2, 2, 4), (2, 4, 2), (2, 4, 2))]:
+        tr = lib.Transcript(1)
+        before = tr.digest()
+        with pytest.raises(lib.ZkdlError):
+            lib.sumcheck_matmul_general(ctx, z(*sh0), z(*sh1), z(*shy), tr)
+        assert tr.digest() == before
+
+
 def _reindex_maps(case, n):
     rng = np.random.default_rng(99)
     if case == "layers":          # inputs of the layers / their outputs: a shift by one tensor
