@@ -444,42 +444,13 @@ __device__ inline void wave_resolve_claim(DevState* st) {
     }
 }
 
-// First part of closing a round: g_t(0..npts-1) (LDS, Montgomery, npts = 2..4) go to the proof
-// and into the transcript, the round's challenge v_t is drawn and returned to every thread.
-// The Lagrange coefficients of g_t are left in S.tmp[0..npts) for the claim g_t(v_t).
-// Needs blockDim.x >= 192: while wave 0 hashes, wave 1 prepares the coefficients and wave 2
-// later writes the canonical form of the challenge.
-__device__ inline Fr block_round_challenge(TsShared& S, DevState* st, const Fr* g, int npts,
-                                           uint32_t proof_off, int chal_idx, char label = 'g',
-                                           bool skip1 = true) {
+// S.canon[0..count) go into the transcript under a one-character label, then one challenge is drawn: it is
+// returned to every thread and stored in st->chal[chal_idx] (Montgomery form) and st->chal_le (canonical).
+// When the unfinished block leaves room, the closing blocks of the draw's hashes are scheduled during the
+// absorb and hashed by lanes 0..2 side by side.  Needs blockDim.x >= 192 (lane 128 writes the canonical form).
+__device__ inline Fr block_absorb_draw1(TsShared& S, DevState* st, char label, int count, int chal_idx) {
     const int tid = threadIdx.x;
-    uint32_t* proof_dst = (uint32_t*)(st->proof + proof_off);
-    __syncthreads();
-    // canonical forms (wave 0) | Lagrange coefficients (wave 1).  The transcript takes
-    // g(0), g(2), .., g(npts-1): g(1) is fixed by the claim the transcript already determines.
-    // (skip1 = false, the f_t of the optimized matrix-product protocol: all evaluations.)
-    if (tid < npts) {
-        Fr plain = fr_from_mont_ni(g[tid]);
-        const int slot = (!skip1 || tid == 0) ? tid : tid - 1;
-#pragma unroll
-        for (int l = 0; l < 8; ++l) {
-            if (!skip1 || tid != 1) S.canon[slot][l] = plain.v[l];
-            proof_dst[8 * tid + l] = plain.v[l];
-        }
-    } else if (tid >= 64 && tid < 64 + npts) {
-        const int k = tid - 64;
-        Fr c = g[k];
-        if (npts == 3) {            // 1/2, -1, 1/2
-            c = (k == 1) ? fr_neg(c) : fr_mul_ni(c, st->inv2);
-        } else if (npts == 4) {     // -1/6, 1/2, -1/2, 1/6
-            c = fr_mul_ni(c, (k == 0 || k == 3) ? st->inv6 : st->inv2);
-            if (k == 0 || k == 2) c = fr_neg(c);
-        } else if (k == 0) {        // -1, 1
-            c = fr_neg(c);
-        }
-        S.tmp[k] = c;
-    }
-    const int prep = block_absorb1(S, label, skip1 ? npts - 1 : npts, true);
+    const int prep = block_absorb1(S, label, count, true);
     Fr v;
     if (prep >= 0) {
         // challenge hashes on the schedules prepared during the absorb: lanes 0, 1 (the two
@@ -528,6 +499,44 @@ __device__ inline Fr block_round_challenge(TsShared& S, DevState* st, const Fr* 
     }
     if (tid == 0) st->chal[chal_idx] = v;
     return v;
+}
+
+// First part of closing a round: g_t(0..npts-1) (LDS, Montgomery, npts = 2..4) go to the proof
+// and into the transcript, the round's challenge v_t is drawn and returned to every thread.
+// The Lagrange coefficients of g_t are left in S.tmp[0..npts) for the claim g_t(v_t).
+// Needs blockDim.x >= 192: while wave 0 hashes, wave 1 prepares the coefficients and wave 2
+// later writes the canonical form of the challenge.
+__device__ inline Fr block_round_challenge(TsShared& S, DevState* st, const Fr* g, int npts,
+                                           uint32_t proof_off, int chal_idx, char label = 'g',
+                                           bool skip1 = true) {
+    const int tid = threadIdx.x;
+    uint32_t* proof_dst = (uint32_t*)(st->proof + proof_off);
+    __syncthreads();
+    // canonical forms (wave 0) | Lagrange coefficients (wave 1).  The transcript takes
+    // g(0), g(2), .., g(npts-1): g(1) is fixed by the claim the transcript already determines.
+    // (skip1 = false, the f_t of the optimized matrix-product protocol: all evaluations.)
+    if (tid < npts) {
+        Fr plain = fr_from_mont_ni(g[tid]);
+        const int slot = (!skip1 || tid == 0) ? tid : tid - 1;
+#pragma unroll
+        for (int l = 0; l < 8; ++l) {
+            if (!skip1 || tid != 1) S.canon[slot][l] = plain.v[l];
+            proof_dst[8 * tid + l] = plain.v[l];
+        }
+    } else if (tid >= 64 && tid < 64 + npts) {
+        const int k = tid - 64;
+        Fr c = g[k];
+        if (npts == 3) {            // 1/2, -1, 1/2
+            c = (k == 1) ? fr_neg(c) : fr_mul_ni(c, st->inv2);
+        } else if (npts == 4) {     // -1/6, 1/2, -1/2, 1/6
+            c = fr_mul_ni(c, (k == 0 || k == 3) ? st->inv6 : st->inv2);
+            if (k == 0 || k == 2) c = fr_neg(c);
+        } else if (k == 0) {        // -1, 1
+            c = fr_neg(c);
+        }
+        S.tmp[k] = c;
+    }
+    return block_absorb_draw1(S, st, label, skip1 ? npts - 1 : npts, chal_idx);
 }
 
 // Closes a round completely: challenge, then the next claim g_t(v_t) in st->claim.

@@ -1,5 +1,5 @@
 // aggregate_verify: the verifier of an aggregated window on the GPU (Sec. 6 names verification time as the
-// open problem: it is sequential).  The program of verify.cuh runs in one lane; the host only moves the
+// open problem: it is sequential).  The program of verify.cuh runs in one block; the host only moves the
 // proof in and the verdict, the challenges and the transcript state out.  zkdl_host_aggregate_verify runs the
 // same program on the CPU (used by the library's tests without a GPU).
 #include <string.h>
@@ -10,27 +10,63 @@
 
 namespace {
 
+constexpr int VERIFY_STAGE_BYTES = 32768;
+
 struct VerifyOut {
     int verdict;
     int n_chal;
     ts::State s;
 };
 
-__global__ __launch_bounds__(64) void k_verify_aggregate(const uint8_t* proof, uint64_t len, ts::State s0, Fr* chal,
-                                                         uint8_t* chal_le, VerifyOut* out) {
-    // one wave; every lane runs the same sequential program (same branches: the proof decides them), the lanes
-    // share out the elements of a draw
-    __shared__ ts::State s_live, s_work;
-    s_live = s0;   // every lane stores the same bytes
+// One block: every thread runs the same sequential program (same branches: the proof decides them); the
+// transcript steps are shared out among the lanes as in the prover's kernels.  The challenges go to st->chal
+// and, canonical, to st->chal_le as they are drawn.
+__global__ __launch_bounds__(ZK_BLOCK) void k_verify_aggregate(const uint8_t* proof, uint64_t len, ts::State s0, DevState* st,
+                                                               VerifyOut* out) {
+    __shared__ TsShared S;
+    __shared__ vf::DevShared D;
+    __shared__ uint32_t staged[VERIFY_STAGE_BYTES / 4];   // the proof, when it fits: every later read is an LDS read
+    const int tid = threadIdx.x;
+    if (len <= (uint64_t)VERIFY_STAGE_BYTES) {
+        const uint32_t nw = (uint32_t)((len + 3) / 4);   // the buffer is padded to a multiple of 256 bytes
+        for (uint32_t i = tid; i < nw; i += blockDim.x) staged[i] = ((const uint32_t*)proof)[i];
+        proof = (const uint8_t*)staged;
+    }
+    if (tid < 8) S.state[tid] = s0.h[tid];
+    if (tid >= 16 && tid < 32) {
+        uint32_t w = 0;
+        for (int b = 0; b < 4; ++b) {
+            const uint32_t at = 4u * (uint32_t)(tid - 16) + (uint32_t)b;
+            w = (w << 8) | (at < s0.fill ? (uint32_t)s0.buf[at] : 0u);
+        }
+        S.buf[0][tid - 16] = w;
+    }
+    if (tid == 8) {
+        S.nblk = s0.nblk;
+        S.fill = s0.fill;
+        S.bufsel = 0;
+    }
     __syncthreads();
-    vf::Ctx c = {s_live, s_work, chal, 0, fr_zero(), fr_zero(), false};
+    vf::DevCtx c;
+    c.chal = st->chal;
+    c.n_chal = 0;
+    c.inv2 = st->inv2;
+    c.inv6 = st->inv6;
+    c.overflow = false;
+    c.S = &S;
+    c.D = &D;
+    c.st = st;
     const int verdict = vf::aggregate(c, proof, (size_t)len);
-    if (threadIdx.x == 0) {
+    __syncthreads();
+    if (tid == 0) {
         out->verdict = verdict;
         out->n_chal = c.n_chal;
-        out->s = c.s;
+        for (int i = 0; i < 8; ++i) out->s.h[i] = S.state[i];
+        out->s.nblk = S.nblk;
+        out->s.fill = S.fill;
+        for (uint32_t i = 0; i < 64; ++i)
+            out->s.buf[i] = i < S.fill ? (uint8_t)(S.buf[S.bufsel][i >> 2] >> (24 - 8 * (i & 3))) : (uint8_t)0;
     }
-    for (int i = threadIdx.x; i < c.n_chal; i += blockDim.x) ts::fr_to_le(chal[i], chal_le + 32 * (size_t)i);
 }
 
 // offsets of the four parts of a "ZKAG" proof and their first challenge indices, from the header
@@ -100,11 +136,16 @@ extern "C" int zkdl_host_aggregate_verify(const uint8_t* proof, size_t proof_len
         delete[] le;
         return ZKDL_ENOMEM;
     }
-    ts::State live = tr->s, work;
-    vf::Ctx c = {live, work, chal, 0, fr_zero(), fr_zero(), false};
+    ts::State live = tr->s;
+    vf::HostCtx c;
+    c.chal = chal;
+    c.n_chal = 0;
+    c.overflow = false;
+    c.s = &live;
+    vf::host_inverses(c.inv2, c.inv6);
     const int v = vf::aggregate(c, proof, proof_len);
     for (int i = 0; i < c.n_chal; ++i) ts::fr_to_le(chal[i], le + 32 * (size_t)i);
-    const int rc = finish_verify(tr, v, c.s, c.n_chal, le, proof, proof_len, verdict, points_out, npoints, claims_out, nclaims);
+    const int rc = finish_verify(tr, v, live, c.n_chal, le, proof, proof_len, verdict, points_out, npoints, claims_out, nclaims);
     delete[] chal;
     delete[] le;
     return rc;
@@ -114,31 +155,29 @@ extern "C" int aggregate_verify(zkdl_ctx* ctx, const uint8_t* proof, size_t proo
                                 zkdl_fr* points_out, size_t* npoints, zkdl_claim* claims_out, size_t* nclaims) {
     if (!ctx || !proof || !tr || !verdict || proof_len == 0 || proof_len > (size_t)ZK_PROOF_CAP) return ZKDL_EINVAL;
     ZK_HIP(ctx, hipSetDevice(ctx->device));
-    uint8_t* d_proof = (uint8_t*)zk_alloc(ctx, proof_len);
-    Fr* d_chal = (Fr*)zk_alloc(ctx, sizeof(Fr) * vf::MAX_CHAL);
-    uint8_t* d_le = (uint8_t*)zk_alloc(ctx, 32 * vf::MAX_CHAL);
+    uint8_t* d_proof = (uint8_t*)zk_alloc(ctx, proof_len);   // 256-byte aligned: the kernel reads whole words
     VerifyOut* d_out = (VerifyOut*)zk_alloc(ctx, sizeof(VerifyOut));
-    int rc = (d_proof && d_chal && d_le && d_out) ? ZKDL_OK : ZKDL_ENOMEM;
+    int rc = (d_proof && d_out) ? ZKDL_OK : ZKDL_ENOMEM;
     VerifyOut h_out;
     memset(&h_out, 0, sizeof h_out);
     uint8_t* h_le = ctx->host_stage;   // pinned; 32 KiB of it
     static_assert(sizeof(DevState) >= 32 * vf::MAX_CHAL, "staging buffer holds the challenges");
+    static_assert(vf::MAX_CHAL <= ZK_MAX_CHAL, "the state block holds the verifier's challenges");
     hipError_t e = hipSuccess;
     if (rc == ZKDL_OK) {
         e = hipMemcpyAsync(d_proof, proof, proof_len, hipMemcpyHostToDevice, ctx->stream);
         if (e == hipSuccess) {
-            hipLaunchKernelGGL(k_verify_aggregate, dim3(1), dim3(64), 0, ctx->stream, d_proof, (uint64_t)proof_len, tr->s, d_chal,
-                               d_le, d_out);
+            hipLaunchKernelGGL(k_verify_aggregate, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, d_proof, (uint64_t)proof_len, tr->s,
+                               ctx->dev, d_out);
             e = hipMemcpyAsync(&h_out, d_out, sizeof h_out, hipMemcpyDeviceToHost, ctx->stream);
         }
-        if (e == hipSuccess) e = hipMemcpyAsync(h_le, d_le, 32 * vf::MAX_CHAL, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(h_le, ctx->dev->chal_le, 32 * vf::MAX_CHAL, hipMemcpyDeviceToHost, ctx->stream);
     }
     hipError_t e2 = hipStreamSynchronize(ctx->stream);
     if (e == hipSuccess) e = e2;
     if (e == hipSuccess) e = hipGetLastError();
     zk_free(ctx, d_proof);
-    zk_free(ctx, d_chal);
-    zk_free(ctx, d_le);
     zk_free(ctx, d_out);
     if (rc != ZKDL_OK) return rc;
     ZK_HIP(ctx, e);

@@ -9,6 +9,9 @@
 #pragma once
 #include "fr.cuh"
 #include "sha256.cuh"
+#if defined(__HIPCC__)
+#include "dev_common.cuh"
+#endif
 
 #define VF_HD __host__ __device__ inline
 // the building blocks are kept out of line on the device: the program runs once, from a cold instruction
@@ -25,37 +28,12 @@ VF_HD Fr mulx(const Fr& a, const Fr& b) {
 #endif
 }
 
-VF_NI void absorb_bytes(ts::State& s, const char* label, uint32_t label_len, const uint8_t* data, uint64_t n) {
-    ts::absorb(s, label, label_len, data, n);
-}
-
-// lanes that run the program side by side (the device runs one wave, every lane the same program; a draw of
-// several challenges is shared out among them)
-VF_HD int lane_id() {
-#if defined(__HIP_DEVICE_COMPILE__)
-    return (int)threadIdx.x;
-#else
-    return 0;
-#endif
-}
-VF_HD int lane_count() {
-#if defined(__HIP_DEVICE_COMPILE__)
-    return (int)blockDim.x;
-#else
-    return 1;
-#endif
-}
-VF_HD void lanes_sync() {
-#if defined(__HIP_DEVICE_COMPILE__)
-    __threadfence_block();
-    __syncthreads();
-#endif
-}
-
 constexpr uint32_t SC_MAGIC = 0x43534B5Au, ZKAG_MAGIC = 0x47414B5Au, ZKAF_MAGIC = 0x46414B5Au, ZKRL_MAGIC = 0x4C524B5Au,
                    FT_MAGIC = 0x46534B5Au;
 constexpr int MAX_CHAL = 1024;
+constexpr int MAX_RD = 4;   // elements one read may take
 
+// the proof: 4-byte aligned on the device, every field at a multiple of four bytes
 struct Reader {
     const uint8_t* p;
     size_t len, at;
@@ -69,115 +47,41 @@ VF_HD uint32_t rd_u32(Reader& r) {
     }
     const uint8_t* q = r.p + r.at;
     r.at += 4;
+#if defined(__HIP_DEVICE_COMPILE__)
+    return *(const uint32_t*)q;
+#else
     return (uint32_t)q[0] | ((uint32_t)q[1] << 8) | ((uint32_t)q[2] << 16) | ((uint32_t)q[3] << 24);
+#endif
 }
 
-// a field element of the proof: 32 canonical little-endian bytes; Montgomery form out, the bytes' position in *src
-VF_NI Fr rd_fr(Reader& r, const uint8_t** src) {
-    Fr x = fr_zero();
-    if (r.at + 32 > r.len) {
-        r.bad = true;
-        return x;
-    }
-    const uint8_t* q = r.p + r.at;
-    if (src) *src = q;
-    r.at += 32;
-    for (int l = 0; l < 8; ++l)
-        x.v[l] = (uint32_t)q[4 * l] | ((uint32_t)q[4 * l + 1] << 8) | ((uint32_t)q[4 * l + 2] << 16) | ((uint32_t)q[4 * l + 3] << 24);
-    bool below = false, above = false;   // canonical: below r
+VF_HD bool below_modulus(const Fr& x) {
+    bool below = false, above = false;
     for (int l = 7; l >= 0; --l) {
         if (below || above) break;
         if (x.v[l] > frc::MOD[l]) above = true;
         else if (x.v[l] < frc::MOD[l]) below = true;
     }
-    if (!below) r.bad = true;
-    return fr_to_mont(x);
-}
-
-struct Ctx {
-    ts::State& s;   // the transcript; on the device it lives in LDS (byte-wise updates of private memory are slow)
-    ts::State& tmp; // work copy for the hashes of a draw, in the same kind of memory
-    Fr* chal;       // room for MAX_CHAL challenges (Montgomery form)
-    int n_chal;
-    Fr inv2, inv6;
-    bool overflow;
-};
-
-VF_HD void absorb_words(Ctx& c, const char* label, uint32_t label_len, const uint32_t* w, int n) {
-    uint8_t b[32];
-    for (int i = 0; i < n; ++i)
-        for (int k = 0; k < 4; ++k) b[4 * i + k] = (uint8_t)(w[i] >> (8 * k));
-    absorb_bytes(c.s, label, label_len, b, 4 * (uint64_t)n);
-}
-
-// element idx of a draw, hashed in the context's work copy of the transcript
-VF_NI Fr challenge_elem(Ctx& c, uint32_t idx) {
-    uint32_t d[2][8];
-    for (uint32_t j = 0; j < 2; ++j) {
-        c.tmp = c.s;
-        ts::State& f = c.tmp;
-        const uint64_t bits = (c.s.nblk * 64 + c.s.fill + 5) * 8;
-        ts::push_byte(f, (uint8_t)(0xF0 + j));
-        for (int k = 0; k < 4; ++k) ts::push_byte(f, (uint8_t)(idx >> (8 * k)));
-        ts::push_byte(f, 0x80);
-        while (f.fill != 56) ts::push_byte(f, 0);
-        for (int i = 7; i >= 0; --i) ts::push_byte(f, (uint8_t)(bits >> (8 * i)));
-        for (int i = 0; i < 8; ++i) d[j][i] = f.h[i];
-    }
-    Fr lo, hi;
-    for (int l = 0; l < 8; ++l) {
-        lo.v[l] = sha::bswap32(d[0][l]);
-        hi.v[l] = sha::bswap32(d[1][l]);
-    }
-    return fr_add(mulx(fr_const(frc::R2), lo), mulx(fr_const(frc::W3), hi));   // lo + 2^256 hi mod r
-}
-
-// one draw of n challenges, appended to c.chal; returns the index of the first
-VF_NI int draw(Ctx& c, int n) {
-    const int base = c.n_chal;
-    if (base + n > MAX_CHAL) {
-        c.overflow = true;
-        return 0;
-    }
-    if (lane_count() == 1) {
-        for (int i = 0; i < n; ++i) c.chal[base + i] = challenge_elem(c, (uint32_t)i);
-    } else if (n == 1) {
-        c.chal[base] = challenge_elem(c, 0);   // every lane the same element, in the shared work copy
-    } else {
-        // each lane its own elements: the work copy is per lane then (private memory)
-        for (int i = lane_id(); i < n; i += lane_count()) c.chal[base + i] = ts::challenge_elem(c.s, (uint32_t)i);
-    }
-    lanes_sync();   // every lane reads every challenge afterwards
-    if (n > 0) ts::ratchet(c.s);
-    c.n_chal += n;
-    return base;
-}
-
-VF_HD int ilog2(uint64_t x) {   // -1 if x is no power of two
-    int l = 0;
-    if (x == 0) return -1;
-    while (((uint64_t)1 << l) < x) ++l;
-    return (((uint64_t)1 << l) == x) ? l : -1;
+    return below;
 }
 
 // value at v of the polynomial through (k, g[k]), k < npts, npts = 3 or 4
-VF_NI Fr lagrange(const Ctx& c, const Fr* g, int npts, const Fr& v) {
+VF_NI Fr lagrange_serial(const Fr& inv2, const Fr& inv6, const Fr* g, int npts, const Fr& v) {
     const Fr one = fr_one();
     const Fr v1 = fr_sub(v, one), v2 = fr_sub(v1, one), v3 = fr_sub(v2, one);
     if (npts == 4) {   // g(v) = (v-2)(v-3) [c0 (v-1) + c1 v] + v (v-1) [c2 (v-3) + c3 (v-2)], c = (-g0/6, g1/2, -g2/2, g3/6)
-        const Fr c0 = fr_neg(mulx(g[0], c.inv6)), c1 = mulx(g[1], c.inv2), c2 = fr_neg(mulx(g[2], c.inv2)),
-                 c3 = mulx(g[3], c.inv6);
+        const Fr c0 = fr_neg(mulx(g[0], inv6)), c1 = mulx(g[1], inv2), c2 = fr_neg(mulx(g[2], inv2)),
+                 c3 = mulx(g[3], inv6);
         const Fr a = mulx(mulx(v2, v3), fr_add(mulx(c0, v1), mulx(c1, v)));
         const Fr b = mulx(mulx(v, v1), fr_add(mulx(c2, v3), mulx(c3, v2)));
         return fr_add(a, b);
     }
     // g(v) = (v-2) [c0 (v-1) + c1 v] + c2 v (v-1), c = (g0/2, -g1, g2/2)
-    const Fr c0 = mulx(g[0], c.inv2), c1 = fr_neg(g[1]), c2 = mulx(g[2], c.inv2);
+    const Fr c0 = mulx(g[0], inv2), c1 = fr_neg(g[1]), c2 = mulx(g[2], inv2);
     return fr_add(mulx(v2, fr_add(mulx(c0, v1), mulx(c1, v))), mulx(c2, mulx(v, v1)));
 }
 
 // beta~(u, v) = prod_k (u_k v_k + (1 - u_k)(1 - v_k))
-VF_NI Fr beta_point(const Fr* u, const Fr* v, int m) {
+VF_NI Fr beta_point_serial(const Fr* u, const Fr* v, int m) {
     Fr acc = fr_one();
     const Fr one = fr_one();
     for (int k = 0; k < m; ++k)
@@ -185,115 +89,8 @@ VF_NI Fr beta_point(const Fr* u, const Fr* v, int m) {
     return acc;
 }
 
-// The rounds of one SC block: every g_t(0) + g_t(1) against the running claim, the challenges re-derived
-// (appended to c.chal).  `claim` holds claim_0 on entry (already checked / absorbed by the caller as the
-// protocol says) and the final claim on return.  first_label: 'g' rounds absorb g(0), g(2), .., g(degree).
-// Returns 0 or a detail code.
-VF_NI int rounds(Ctx& c, Reader& r, int nrounds, int degree, Fr& claim, int* first_chal) {
-    *first_chal = c.n_chal;
-    for (int t = 0; t < nrounds; ++t) {
-        Fr g[4];
-        const uint8_t* src[4];
-        for (int x = 0; x <= degree; ++x) g[x] = rd_fr(r, &src[x]);
-        if (r.bad) return 1;
-        if (!fr_eq(fr_add(g[0], g[1]), claim)) return 2;   // Sec. 2.2
-        uint8_t msg[96];
-        int nm = 0;
-        for (int x = 0; x <= degree; ++x) {
-            if (x == 1) continue;
-            for (int b = 0; b < 32; ++b) msg[32 * nm + b] = src[x][b];
-            ++nm;
-        }
-        absorb_bytes(c.s, "g", 1, msg, 32 * (uint64_t)nm);
-        const int ci = draw(c, 1);
-        if (c.overflow) return 3;
-        claim = lagrange(c, g, degree + 1, c.chal[ci]);
-    }
-    return 0;
-}
-
-struct ScHeader {
-    uint32_t n_finals, degree, rounds;
-};
-
-VF_HD bool rd_sc_header(Reader& r, ScHeader& h) {
-    const uint32_t magic = rd_u32(r);
-    h.n_finals = rd_u32(r);
-    h.degree = rd_u32(r);
-    h.rounds = rd_u32(r);
-    return !r.bad && magic == SC_MAGIC;
-}
-
-// Eq. exm-matmul-batched, the prover's g_t form: header, draw (w, u0, u1), claim_0, rounds over (n, i), the
-// finals (beta~(w, v_n), X0~, X1~) with beta~(w, v_n) recomputed and their product against the last claim.
-VF_NI int matmul(Ctx& c, Reader& r, uint64_t n, uint64_t d1, uint64_t d2, uint64_t d3) {
-    const int ln = ilog2(n), l1 = ilog2(d1), l2 = ilog2(d2), l3 = ilog2(d3);
-    ScHeader h;
-    if (!rd_sc_header(r, h) || h.n_finals != 3 || h.degree != 3 || (int)h.rounds != ln + l2) return 10;
-    const uint32_t words[4] = {(uint32_t)n, (uint32_t)d1, (uint32_t)d2, (uint32_t)d3};
-    absorb_words(c, "sumcheck_matmul", 15, words, 4);
-    const int cw = draw(c, ln + l1 + l3);
-    const uint8_t* src;
-    Fr claim = rd_fr(r, &src);
-    if (r.bad || c.overflow) return 11;
-    absorb_bytes(c.s, "c", 1, src, 32);
-    int cv;
-    const int rc = rounds(c, r, ln + l2, 3, claim, &cv);
-    if (rc) return 20 + rc;
-    const uint8_t* fsrc;
-    const Fr fb = rd_fr(r, &fsrc), f0 = rd_fr(r, nullptr), f1 = rd_fr(r, nullptr);
-    if (r.bad) return 12;
-    absorb_bytes(c.s, "f", 1, fsrc, 96);
-    if (!fr_eq(fb, beta_point(c.chal + cw, c.chal + cv, ln))) return 13;
-    if (!fr_eq(mulx(mulx(fb, f0), f1), claim)) return 14;
-    return 0;
-}
-
-// The optimized aggregated protocol (App. B): stack rounds with f_t, (1 - w_t) f_t(0) + w_t f_t(1) = claim,
-// then the single product's sumcheck (K = 2), whose claim_0 must be f_{n-1}(v_{n-1}).
-VF_NI int matmul_ft(Ctx& c, Reader& r, uint64_t n, uint64_t d1, uint64_t d2, uint64_t d3) {
-    const int ln = ilog2(n), l1 = ilog2(d1), l2 = ilog2(d2), l3 = ilog2(d3);
-    const uint32_t magic = rd_u32(r), pln = rd_u32(r), pl2 = rd_u32(r), zero = rd_u32(r);
-    if (r.bad || magic != FT_MAGIC || (int)pln != ln || (int)pl2 != l2 || zero != 0) return 10;
-    const uint32_t words[4] = {(uint32_t)n, (uint32_t)d1, (uint32_t)d2, (uint32_t)d3};
-    absorb_words(c, "sumcheck_matmul_ft", 18, words, 4);
-    const int cw = draw(c, ln + l1 + l3);
-    const uint8_t* src;
-    Fr claim = rd_fr(r, &src);
-    if (r.bad || c.overflow) return 11;
-    absorb_bytes(c.s, "c", 1, src, 32);
-    const Fr one = fr_one();
-    for (int t = 0; t < ln; ++t) {
-        Fr f[3];
-        const uint8_t* fs;
-        f[0] = rd_fr(r, &fs);
-        f[1] = rd_fr(r, nullptr);
-        f[2] = rd_fr(r, nullptr);
-        if (r.bad) return 15;
-        const Fr wt = c.chal[cw + t];
-        if (!fr_eq(fr_add(mulx(fr_sub(one, wt), f[0]), mulx(wt, f[1])), claim)) return 16;
-        absorb_bytes(c.s, "f", 1, fs, 96);
-        const int ci = draw(c, 1);
-        if (c.overflow) return 17;
-        claim = lagrange(c, f, 3, c.chal[ci]);
-    }
-    ScHeader h;
-    if (!rd_sc_header(r, h) || h.n_finals != 2 || h.degree != 2 || (int)h.rounds != l2) return 18;
-    Fr inner0 = rd_fr(r, nullptr);
-    if (r.bad || !fr_eq(inner0, claim)) return 19;
-    int cv;
-    const int rc = rounds(c, r, l2, 2, claim, &cv);
-    if (rc) return 20 + rc;
-    const uint8_t* fsrc;
-    const Fr f0 = rd_fr(r, &fsrc), f1 = rd_fr(r, nullptr);
-    if (r.bad) return 12;
-    absorb_bytes(c.s, "f", 1, fsrc, 64);
-    if (!fr_eq(mulx(f0, f1), claim)) return 14;
-    return 0;
-}
-
 // multilinear extension of a table of J = 2^lj signed integers at wbar: sum_j tab[j] beta~(wbar, j)
-VF_NI Fr mle_small(const Fr* tab, int lj, const Fr* wbar) {
+VF_NI Fr mle_small_serial(const Fr* tab, int lj, const Fr* wbar) {
     Fr beta[64];
     beta[0] = fr_one();
     int len = 1;
@@ -311,8 +108,383 @@ VF_NI Fr mle_small(const Fr* tab, int lj, const Fr* wbar) {
     return acc;
 }
 
+// What the program needs from its surroundings: the transcript, the challenges drawn so far, reading field
+// elements of the proof.  Two implementations with the same members:
+//   HostCtx  one thread, the byte-wise transcript of the host side;
+//   DevCtx   one block of 256 threads that all run the program (same branches: the proof decides them) and
+//            share the transcript steps out as the prover's kernels do.
+//   rd_elems(r, n, out, src)        n <= MAX_RD consecutive elements: canonical (else r.bad), Montgomery form out
+//   absorb_words(label, len, w, n)  a header frame of n <= 8 words
+//   absorb_elems(label, src, n)     n elements as they stand in the proof, one-character label
+//   absorb_draw1(label, src, n, skip1, v)  the same (skip1: without element 1), then a draw of one challenge
+//   draw(n)                         a draw of n challenges; both return the index of the first
+//   lagrange(g, npts, v), beta_point(u, v, m), mle_small(tab, lj, wbar)   the verifier's own arithmetic: serial on
+//                                   the host, one term per lane on the device
+struct CtxBase {
+    Fr* chal;       // room for MAX_CHAL challenges (Montgomery form)
+    int n_chal;
+    Fr inv2, inv6;
+    bool overflow;
+};
+
+struct HostCtx : CtxBase {
+    ts::State* s;
+
+    __host__ void rd_elems(Reader& r, int n, Fr* out, const uint8_t** src) {
+        for (int e = 0; e < n; ++e) out[e] = fr_zero();
+        if (r.at + 32 * (size_t)n > r.len) {
+            r.bad = true;
+            return;
+        }
+        const uint8_t* q = r.p + r.at;
+        if (src) *src = q;
+        r.at += 32 * (size_t)n;
+        for (int e = 0; e < n; ++e) {
+            Fr x;
+            for (int l = 0; l < 8; ++l) {
+                const uint8_t* b = q + 32 * e + 4 * l;
+                x.v[l] = (uint32_t)b[0] | ((uint32_t)b[1] << 8) | ((uint32_t)b[2] << 16) | ((uint32_t)b[3] << 24);
+            }
+            if (!below_modulus(x)) r.bad = true;
+            out[e] = fr_to_mont(x);
+        }
+    }
+    __host__ void absorb_words(const char* label, uint32_t label_len, const uint32_t* w, int n) {
+        uint8_t b[32];
+        for (int i = 0; i < n; ++i)
+            for (int k = 0; k < 4; ++k) b[4 * i + k] = (uint8_t)(w[i] >> (8 * k));
+        ts::absorb(*s, label, label_len, b, 4 * (uint64_t)n);
+    }
+    __host__ void absorb_elems(char label, const uint8_t* src, int n) { ts::absorb(*s, &label, 1, src, 32 * (uint64_t)n); }
+    __host__ int draw(int n) {
+        const int base = n_chal;
+        if (base + n > MAX_CHAL) {
+            overflow = true;
+            return 0;
+        }
+        for (int i = 0; i < n; ++i) chal[base + i] = ts::challenge_elem(*s, (uint32_t)i);
+        if (n > 0) ts::ratchet(*s);
+        n_chal += n;
+        return base;
+    }
+    __host__ Fr lagrange(const Fr* g, int npts, const Fr& v) const { return lagrange_serial(inv2, inv6, g, npts, v); }
+    __host__ Fr beta_point(const Fr* u, const Fr* v, int m) const { return beta_point_serial(u, v, m); }
+    __host__ Fr mle_small(const Fr* tab, int lj, const Fr* wbar) const { return mle_small_serial(tab, lj, wbar); }
+    __host__ int absorb_draw1(char label, const uint8_t* src, int n, bool skip1, Fr* v) {
+        uint8_t msg[32 * MAX_RD];
+        int nm = 0;
+        for (int e = 0; e < n; ++e) {
+            if (skip1 && e == 1) continue;
+            for (int b = 0; b < 32; ++b) msg[32 * nm + b] = src[32 * e + b];
+            ++nm;
+        }
+        ts::absorb(*s, &label, 1, msg, 32 * (uint64_t)nm);
+        const int ci = draw(1);
+        *v = overflow ? fr_zero() : chal[ci];
+        return ci;
+    }
+};
+
+#if defined(__HIPCC__)
+// LDS of the device side next to the transcript's
+struct DevShared {
+    Fr mont[MAX_RD];
+    uint32_t bad[MAX_RD];
+    uint32_t words[8];
+};
+
+// The block-wide transcript steps, kept out of line (one copy each) and given only pointers and scalars, so
+// that a caller's own state can stay in registers across them.
+__device__ __noinline__ inline void dev_absorb1(TsShared* S, char label, int n) { block_absorb1(*S, label, n, false); }
+__device__ __noinline__ inline Fr dev_absorb_draw1(TsShared* S, DevState* st, char label, int count, int ci) {
+    return block_absorb_draw1(*S, st, label, count, ci);
+}
+__device__ __noinline__ inline void dev_challenges(TsShared* S, DevState* st, int base, int n) {
+    block_challenges(*S, st, base, n);
+}
+__device__ __noinline__ inline Fr dev_wave_lagrange(const Fr* coef, int npts, Fr v) { return wave_lagrange(coef, npts, v); }
+
+struct DevCtx : CtxBase {
+    TsShared* S;
+    DevShared* D;
+    DevState* st;   // chal = st->chal; the canonical forms go to st->chal_le as they are drawn
+
+    __device__ __forceinline__ static Fr lane0(const Fr& x) {   // lane 0's value to every lane of the wave
+        Fr y;
+        for (int l = 0; l < 8; ++l) y.v[l] = __shfl(x.v[l], 0, 64);
+        return y;
+    }
+    // g(v) with one coefficient per lane and the two-level evaluation of the prover's kernels; every wave does
+    // the same, so nothing goes through memory afterwards
+    __device__ __forceinline__ Fr lagrange(const Fr* g, int npts, const Fr& v) {
+        const int tid = threadIdx.x;
+        __syncthreads();
+        if (tid < npts) {
+            Fr ck = tid == 0 ? g[0] : tid == 1 ? g[1] : tid == 2 ? g[2] : g[3];
+            if (npts == 3) {
+                ck = (tid == 1) ? fr_neg(ck) : mulx(ck, inv2);
+            } else {
+                ck = mulx(ck, (tid == 0 || tid == 3) ? inv6 : inv2);
+                if (tid == 0 || tid == 2) ck = fr_neg(ck);
+            }
+            S->tmp[tid] = ck;
+        }
+        __syncthreads();
+        return lane0(dev_wave_lagrange(S->tmp, npts, v));
+    }
+    // product of the lanes' values over a wave (lane 0 holds it)
+    __device__ static Fr wave_product(Fr x) {
+        for (int off = 32; off >= 1; off >>= 1) {
+            Fr y;
+            for (int l = 0; l < 8; ++l) y.v[l] = __shfl_down(x.v[l], off, 64);
+            x = mulx(x, y);
+        }
+        return x;
+    }
+    // u, v: the same values in every thread (challenges, or arrays every thread has built alike)
+    __device__ Fr beta_point(const Fr* u, const Fr* v, int m) {
+        const int lane = threadIdx.x & 63;
+        const Fr one = fr_one();
+        Fr acc = one;
+        for (int k0 = 0; k0 < m; k0 += 64) {
+            Fr t = one;
+            if (k0 + lane < m) {
+                const Fr a = u[k0 + lane], b = v[k0 + lane];
+                t = fr_add(mulx(a, b), mulx(fr_sub(one, a), fr_sub(one, b)));
+            }
+            acc = mulx(acc, lane0(wave_product(t)));
+        }
+        return acc;
+    }
+    __device__ Fr mle_small(const Fr* tab, int lj, const Fr* wbar) {   // lj <= 6
+        const int lane = threadIdx.x & 63;
+        const Fr one = fr_one();
+        Fr t = fr_zero();
+        if (lane < (1 << lj)) {
+            t = tab[lane];
+            for (int k = 0; k < lj; ++k)   // coordinate 0 pairs with the most significant bit
+                t = mulx(t, ((lane >> (lj - 1 - k)) & 1) ? wbar[k] : fr_sub(one, wbar[k]));
+        }
+        for (int off = 32; off >= 1; off >>= 1) {
+            Fr y;
+            for (int l = 0; l < 8; ++l) y.v[l] = __shfl_down(t.v[l], off, 64);
+            t = fr_add(t, y);
+        }
+        return lane0(t);
+    }
+
+    __device__ __forceinline__ void rd_elems(Reader& r, int n, Fr* out, const uint8_t** src) {
+        const int tid = threadIdx.x;
+#pragma unroll
+        for (int e = 0; e < MAX_RD; ++e)
+            if (e < n) out[e] = fr_zero();
+        if (r.at + 32 * (size_t)n > r.len) {
+            r.bad = true;
+            return;
+        }
+        const uint32_t* q = (const uint32_t*)(r.p + r.at);   // LDS when the kernel has staged the proof there
+        if (src) *src = (const uint8_t*)q;
+        r.at += 32 * (size_t)n;
+        __syncthreads();   // the arrays may still be read from the call before
+        if (tid < n) {     // one lane per element
+            Fr x;
+            for (int l = 0; l < 8; ++l) x.v[l] = q[8 * tid + l];
+            D->bad[tid] = below_modulus(x) ? 0u : 1u;
+            D->mont[tid] = mulx(fr_const(frc::R2), x);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < MAX_RD; ++e) {
+            if (e < n) {
+                out[e] = D->mont[e];
+                if (D->bad[e]) r.bad = true;
+            }
+        }
+    }
+    __device__ void absorb_words(const char* label, uint32_t label_len, const uint32_t* w, int n) {
+        __syncthreads();
+        if (threadIdx.x < (unsigned)n) D->words[threadIdx.x] = w[threadIdx.x];
+        const uint32_t data_len = 4u * (uint32_t)n;
+        const DevShared* d = D;
+        auto frame = [=](uint32_t q) -> uint32_t {
+            if (q == 0) return label_len;
+            if (q <= label_len) return (uint32_t)(uint8_t)label[q - 1];
+            const uint32_t k = q - 1 - label_len;
+            if (k < 8) return k < 4 ? (data_len >> (8 * k)) & 0xffu : 0u;
+            const uint32_t b = k - 8;
+            return (d->words[b >> 2] >> (8 * (b & 3))) & 0xffu;
+        };
+        block_append(*S, 1u + label_len + 8u + data_len, frame, false);
+    }
+    __device__ __forceinline__ void fill_canon(const uint8_t* src, int n, bool skip1) {
+        __syncthreads();
+        const int tid = threadIdx.x;
+        if (tid < 8 * n) {
+            const int e = tid >> 3;
+            if (!(skip1 && e == 1)) S->canon[(skip1 && e > 1) ? e - 1 : e][tid & 7] = ((const uint32_t*)src)[tid];
+        }
+    }
+    __device__ __forceinline__ void absorb_elems(char label, const uint8_t* src, int n) {
+        fill_canon(src, n, false);
+        dev_absorb1(S, label, n);
+    }
+    __device__ __forceinline__ int draw(int n) {
+        const int base = n_chal;
+        if (base + n > MAX_CHAL) {
+            overflow = true;
+            return 0;
+        }
+        dev_challenges(S, st, base, n);
+        __threadfence_block();   // every thread reads every challenge afterwards
+        __syncthreads();
+        n_chal += n;
+        return base;
+    }
+    __device__ __forceinline__ int absorb_draw1(char label, const uint8_t* src, int n, bool skip1, Fr* v) {
+        const int ci = n_chal;
+        if (ci + 1 > MAX_CHAL) {
+            overflow = true;
+            *v = fr_zero();
+            return 0;
+        }
+        fill_canon(src, n, skip1);
+        *v = dev_absorb_draw1(S, st, label, skip1 ? n - 1 : n, ci);
+        __threadfence_block();
+        __syncthreads();
+        n_chal += 1;
+        return ci;
+    }
+};
+#endif
+
+VF_HD int ilog2(uint64_t x) {   // -1 if x is no power of two
+    int l = 0;
+    if (x == 0) return -1;
+    while (((uint64_t)1 << l) < x) ++l;
+    return (((uint64_t)1 << l) == x) ? l : -1;
+}
+
+// The rounds of one SC block: every g_t(0) + g_t(1) against the running claim, the challenges re-derived
+// (appended to c.chal).  `claim` holds claim_0 on entry (already checked / absorbed by the caller as the
+// protocol says) and the final claim on return.  The rounds absorb g(0), g(2), .., g(degree) under "g".
+// Returns 0 or a detail code.
+template <class C>
+VF_NI int rounds(C& c_io, Reader& r_io, int nrounds, int degree, Fr& claim_io, int* first_chal) {
+    // work on copies: the caller's objects live in memory, these in registers
+    C c = c_io;
+    Reader r = r_io;
+    Fr claim = claim_io;
+    *first_chal = c.n_chal;
+    int rc = 0;
+    for (int t = 0; t < nrounds && rc == 0; ++t) {
+        Fr g[MAX_RD];
+        const uint8_t* src = nullptr;
+        c.rd_elems(r, degree + 1, g, &src);
+        if (r.bad) {
+            rc = 1;
+        } else if (!fr_eq(fr_add(g[0], g[1]), claim)) {   // Sec. 2.2
+            rc = 2;
+        } else {
+            Fr v;
+            c.absorb_draw1('g', src, degree + 1, true, &v);
+            if (c.overflow) rc = 3;
+            else claim = c.lagrange(g, degree + 1, v);
+        }
+    }
+    c_io = c;
+    r_io = r;
+    claim_io = claim;
+    return rc;
+}
+
+struct ScHeader {
+    uint32_t n_finals, degree, rounds;
+};
+
+VF_HD bool rd_sc_header(Reader& r, ScHeader& h) {
+    const uint32_t magic = rd_u32(r);
+    h.n_finals = rd_u32(r);
+    h.degree = rd_u32(r);
+    h.rounds = rd_u32(r);
+    return !r.bad && magic == SC_MAGIC;
+}
+
+// Eq. exm-matmul-batched, the prover's g_t form: header, draw (w, u0, u1), claim_0, rounds over (n, i), the
+// finals (beta~(w, v_n), X0~, X1~) with beta~(w, v_n) recomputed and their product against the last claim.
+template <class C>
+VF_NI int matmul(C& c, Reader& r, uint64_t n, uint64_t d1, uint64_t d2, uint64_t d3) {
+    const int ln = ilog2(n), l1 = ilog2(d1), l2 = ilog2(d2), l3 = ilog2(d3);
+    ScHeader h;
+    if (!rd_sc_header(r, h) || h.n_finals != 3 || h.degree != 3 || (int)h.rounds != ln + l2) return 10;
+    const uint32_t words[4] = {(uint32_t)n, (uint32_t)d1, (uint32_t)d2, (uint32_t)d3};
+    c.absorb_words("sumcheck_matmul", 15, words, 4);
+    const int cw = c.draw(ln + l1 + l3);
+    const uint8_t* src = nullptr;
+    Fr claim;
+    c.rd_elems(r, 1, &claim, &src);
+    if (r.bad || c.overflow) return 11;
+    c.absorb_elems('c', src, 1);
+    int cv;
+    const int rc = rounds(c, r, ln + l2, 3, claim, &cv);
+    if (rc) return 20 + rc;
+    const uint8_t* fsrc = nullptr;
+    Fr f[3];
+    c.rd_elems(r, 3, f, &fsrc);
+    if (r.bad) return 12;
+    c.absorb_elems('f', fsrc, 3);
+    if (!fr_eq(f[0], c.beta_point(c.chal + cw, c.chal + cv, ln))) return 13;
+    if (!fr_eq(mulx(mulx(f[0], f[1]), f[2]), claim)) return 14;
+    return 0;
+}
+
+// The optimized aggregated protocol (App. B): stack rounds with f_t, (1 - w_t) f_t(0) + w_t f_t(1) = claim,
+// then the single product's sumcheck (K = 2), whose claim_0 must be f_{n-1}(v_{n-1}).
+template <class C>
+VF_NI int matmul_ft(C& c, Reader& r, uint64_t n, uint64_t d1, uint64_t d2, uint64_t d3) {
+    const int ln = ilog2(n), l1 = ilog2(d1), l2 = ilog2(d2), l3 = ilog2(d3);
+    const uint32_t magic = rd_u32(r), pln = rd_u32(r), pl2 = rd_u32(r), zero = rd_u32(r);
+    if (r.bad || magic != FT_MAGIC || (int)pln != ln || (int)pl2 != l2 || zero != 0) return 10;
+    const uint32_t words[4] = {(uint32_t)n, (uint32_t)d1, (uint32_t)d2, (uint32_t)d3};
+    c.absorb_words("sumcheck_matmul_ft", 18, words, 4);
+    const int cw = c.draw(ln + l1 + l3);
+    const uint8_t* src = nullptr;
+    Fr claim;
+    c.rd_elems(r, 1, &claim, &src);
+    if (r.bad || c.overflow) return 11;
+    c.absorb_elems('c', src, 1);
+    const Fr one = fr_one();
+    for (int t = 0; t < ln; ++t) {
+        Fr f[3];
+        const uint8_t* fs = nullptr;
+        c.rd_elems(r, 3, f, &fs);
+        if (r.bad) return 15;
+        const Fr wt = c.chal[cw + t];
+        if (!fr_eq(fr_add(mulx(fr_sub(one, wt), f[0]), mulx(wt, f[1])), claim)) return 16;
+        Fr v;
+        c.absorb_draw1('f', fs, 3, false, &v);
+        if (c.overflow) return 17;
+        claim = c.lagrange(f, 3, v);
+    }
+    ScHeader h;
+    if (!rd_sc_header(r, h) || h.n_finals != 2 || h.degree != 2 || (int)h.rounds != l2) return 18;
+    Fr inner0;
+    c.rd_elems(r, 1, &inner0, nullptr);
+    if (r.bad || !fr_eq(inner0, claim)) return 19;
+    int cv;
+    const int rc = rounds(c, r, l2, 2, claim, &cv);
+    if (rc) return 20 + rc;
+    const uint8_t* fsrc = nullptr;
+    Fr f[2];
+    c.rd_elems(r, 2, f, &fsrc);
+    if (r.bad) return 12;
+    c.absorb_elems('f', fsrc, 2);
+    if (!fr_eq(mulx(f[0], f[1]), claim)) return 14;
+    return 0;
+}
+
 // zkReLU with all five points drawn (App. A and the merge of the three claims on aux)
-VF_NI int zkrelu(Ctx& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r_expect) {
+template <class C>
+VF_NI int zkrelu(C& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r_expect) {
     const uint32_t magic = rd_u32(r), pli = rd_u32(r), q = rd_u32(r), rb = rd_u32(r), has_ga = rd_u32(r), mode = rd_u32(r);
     const uint32_t pad0 = rd_u32(r), pad1 = rd_u32(r);
     if (r.bad || pad0 != 0 || pad1 != 0 || magic != ZKRL_MAGIC || (int)pli != li_expect || q != q_expect || rb != r_expect || mode != 0 || has_ga > 1)
@@ -322,30 +494,33 @@ VF_NI int zkrelu(Ctx& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r
     int lj = 0;
     while ((1 << lj) < b) ++lj;
     const int J = 1 << lj;
-    const uint8_t* csrc;
+    const uint8_t* csrc = nullptr;
     Fr c_in[4];
-    c_in[0] = rd_fr(r, &csrc);
-    for (int k = 1; k < 4; ++k) c_in[k] = rd_fr(r, nullptr);
+    c.rd_elems(r, 4, c_in, &csrc);
     ScHeader h, hm;
     if (!rd_sc_header(r, h) || h.n_finals != 3 || h.degree != 3 || (int)h.rounds != li + lj) return 2;
     const uint32_t words[4] = {pli, q, rb, has_ga};
-    absorb_words(c, "zkrelu", 6, words, 4);
-    const int cu = draw(c, 5 * li + lj);   // u_Z, u_A, u_GA, u_GZ (li each), u_bin (li + lj)
-    absorb_bytes(c.s, "c", 1, csrc, 128);
-    const int cr = draw(c, 2);
+    c.absorb_words("zkrelu", 6, words, 4);
+    const int cu = c.draw(5 * li + lj);   // u_Z, u_A, u_GA, u_GZ (li each), u_bin (li + lj)
+    if (r.bad || c.overflow) return 3;
+    c.absorb_elems('c', csrc, 4);
+    const int cr = c.draw(2);
     if (c.overflow) return 3;
     const Fr rr = c.chal[cr], rp = c.chal[cr + 1], r2 = mulx(rr, rr);
     const Fr w_z = r2, w_a = rr, w_ga = mulx(rp, r2), w_gz = mulx(rp, rr);
-    Fr claim = rd_fr(r, nullptr);
+    Fr claim;
+    c.rd_elems(r, 1, &claim, nullptr);
     const Fr expect0 = fr_add(fr_add(mulx(w_z, c_in[0]), mulx(w_a, c_in[1])), fr_add(mulx(w_ga, c_in[2]), mulx(w_gz, c_in[3])));
     if (r.bad || !fr_eq(claim, expect0)) return 4;   // the combined claim is the weighted sum of the input claims
     int cv;
     int rc = rounds(c, r, li + lj, 3, claim, &cv);
     if (rc) return 10 + rc;
-    const uint8_t* fsrc;
-    const Fr a0 = rd_fr(r, &fsrc), a1 = rd_fr(r, nullptr), sg = rd_fr(r, nullptr);
+    const uint8_t* fsrc = nullptr;
+    Fr fin[3];
+    c.rd_elems(r, 3, fin, &fsrc);
     if (r.bad) return 5;
-    absorb_bytes(c.s, "f", 1, fsrc, 96);
+    const Fr a0 = fin[0], a1 = fin[1], sg = fin[2];
+    c.absorb_elems('f', fsrc, 3);
     // s_{Q+R} = (1, 2, .., 2^(B-2), -2^(B-1)) and s' = (0^(R-1), 1, 1, 2, .., 2^(Q-2), -2^(Q-1)), zero-padded
     Fr s_tab[64], sp_tab[64];
     for (int j = 0; j < J; ++j) s_tab[j] = sp_tab[j] = fr_zero();
@@ -364,34 +539,37 @@ VF_NI int zkrelu(Ctx& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r
     sp_tab[b - 1] = fr_neg(pw);                    // pw = 2^(Q-1)
     const Fr* v_i = c.chal + cv;
     const Fr* wbar = c.chal + cv + li;
-    const Fr s_w = mle_small(s_tab, lj, wbar), sp_w = mle_small(sp_tab, lj, wbar);
-    const Fr b_bin = beta_point(c.chal + cu + 4 * li, c.chal + cv, li + lj);
+    const Fr s_w = c.mle_small(s_tab, lj, wbar), sp_w = c.mle_small(sp_tab, lj, wbar);
+    const Fr b_bin = c.beta_point(c.chal + cu + 4 * li, c.chal + cv, li + lj);
     const Fr one = fr_one();
     const Fr ns = fr_sub(one, sg);
     auto side = [&](const Fr& a, const Fr& w_in, const Fr& w_out, const Fr* u_in, const Fr* u_out) {
-        Fr t = mulx(mulx(mulx(w_in, beta_point(u_in, v_i, li)), a), s_w);
-        t = fr_add(t, mulx(mulx(mulx(mulx(w_out, beta_point(u_out, v_i, li)), ns), a), sp_w));
+        Fr t = mulx(mulx(mulx(w_in, c.beta_point(u_in, v_i, li)), a), s_w);
+        t = fr_add(t, mulx(mulx(mulx(mulx(w_out, c.beta_point(u_out, v_i, li)), ns), a), sp_w));
         return fr_add(t, mulx(b_bin, fr_sub(mulx(a, a), a)));
     };
     const Fr fwd = side(a0, w_z, w_a, c.chal + cu, c.chal + cu + li);
-    Fr bwd = mulx(mulx(mulx(w_ga, beta_point(c.chal + cu + 2 * li, v_i, li)), a1), s_w);
-    bwd = fr_add(bwd, mulx(mulx(mulx(mulx(w_gz, beta_point(c.chal + cu + 3 * li, v_i, li)), ns), a1), sp_w));
+    Fr bwd = mulx(mulx(mulx(w_ga, c.beta_point(c.chal + cu + 2 * li, v_i, li)), a1), s_w);
+    bwd = fr_add(bwd, mulx(mulx(mulx(mulx(w_gz, c.beta_point(c.chal + cu + 3 * li, v_i, li)), ns), a1), sp_w));
     bwd = fr_add(bwd, mulx(mulx(rp, b_bin), fr_sub(mulx(a1, a1), a1)));
     if (!fr_eq(fr_add(fwd, bwd), claim)) return 6;   // App. A: the six equations at the challenge point
     // merge of the three claims on aux (degree 2 over 1 + lj variables)
     if (!rd_sc_header(r, hm) || hm.n_finals != 2 || hm.degree != 2 || (int)hm.rounds != 1 + lj) return 7;
-    const int crho = draw(c, 3);
+    const int crho = c.draw(3);
     if (c.overflow) return 3;
-    Fr mclaim = rd_fr(r, nullptr);
+    Fr mclaim;
+    c.rd_elems(r, 1, &mclaim, nullptr);
     const Fr em = fr_add(fr_add(mulx(c.chal[crho], a0), mulx(c.chal[crho + 1], a1)), mulx(c.chal[crho + 2], sg));
     if (r.bad || !fr_eq(mclaim, em)) return 8;
     int cm;
     rc = rounds(c, r, 1 + lj, 2, mclaim, &cm);
     if (rc) return 100 + rc;
-    const uint8_t* msrc;
-    const Fr m_f = rd_fr(r, &msrc), e_f = rd_fr(r, nullptr);
+    const uint8_t* msrc = nullptr;
+    Fr mf[2];
+    c.rd_elems(r, 2, mf, &msrc);
     if (r.bad) return 5;
-    absorb_bytes(c.s, "f", 1, msrc, 64);
+    const Fr m_f = mf[0], e_f = mf[1];
+    c.absorb_elems('f', msrc, 2);
     // E~ at the merge's point: rho0 beta~((0, wbar), vm) + rho1 beta~((1, wbar), vm) + rho2 beta~((0, e_{B-1}), vm)
     Fr p0[8], p1[8], p2[8];
     p0[0] = fr_zero();
@@ -403,28 +581,24 @@ VF_NI int zkrelu(Ctx& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r
         p2[1 + k] = (((b - 1) >> (lj - 1 - k)) & 1) ? fr_one() : fr_zero();
     }
     const Fr* vm = c.chal + cm;
-    const Fr e_pub = fr_add(fr_add(mulx(c.chal[crho], beta_point(p0, vm, 1 + lj)), mulx(c.chal[crho + 1], beta_point(p1, vm, 1 + lj))),
-                            mulx(c.chal[crho + 2], beta_point(p2, vm, 1 + lj)));
+    const Fr e_pub = fr_add(fr_add(mulx(c.chal[crho], c.beta_point(p0, vm, 1 + lj)), mulx(c.chal[crho + 1], c.beta_point(p1, vm, 1 + lj))),
+                            mulx(c.chal[crho + 2], c.beta_point(p2, vm, 1 + lj)));
     if (!fr_eq(e_f, e_pub)) return 101;
     if (!fr_eq(mulx(m_f, e_f), mclaim)) return 102;
     return 0;
 }
 
-// The whole window ("ZKAG": g_t form; "ZKAF": f_t form for the matrix products).  c.s is the transcript before
-// the proof and after it on return; c.chal / c.n_chal every challenge in draw order.
-VF_HD int aggregate(Ctx& c, const uint8_t* proof, size_t len) {
+// The whole window ("ZKAG": g_t form; "ZKAF": f_t form for the matrix products).  The context's transcript is
+// the one before the proof and, on return, after it; c.chal / c.n_chal every challenge in draw order; c.inv2 and
+// c.inv6 are 1/2 and 1/6 (checked here).
+template <class C>
+VF_HD int aggregate(C& c, const uint8_t* proof, size_t len) {
     Reader r = {proof, len, 0, false};
     c.n_chal = 0;
     c.overflow = false;
-    {   // 1/2 and 1/6 by Fermat
-        uint32_t e[8];
-        for (int i = 0; i < 8; ++i) e[i] = frc::MOD[i];
-        e[0] = 0xffffffffu;   // r - 2: r[0] = 1 borrows from the next limb, which is 0xffffffff
-        e[1] -= 1u;
+    {
         const Fr two = fr_add(fr_one(), fr_one());
         const Fr six = fr_add(fr_add(two, two), two);
-        c.inv2 = fr_pow(two, e);
-        c.inv6 = fr_pow(six, e);
         if (!fr_eq(mulx(c.inv2, two), fr_one()) || !fr_eq(mulx(c.inv6, six), fr_one())) return 199;
     }
     const uint32_t magic = rd_u32(r), L = rd_u32(r), B = rd_u32(r), width = rd_u32(r), T = rd_u32(r), Q = rd_u32(r), R = rd_u32(r);
@@ -433,8 +607,8 @@ VF_HD int aggregate(Ctx& c, const uint8_t* proof, size_t len) {
     if (ilog2(L) < 0 || ilog2(B) < 0 || ilog2(width) < 0 || ilog2(T) < 0) return 101;
     const bool ft = magic == ZKAF_MAGIC;
     const uint32_t words[6] = {L, B, width, T, Q, R};
-    if (ft) absorb_words(c, "aggregate_ft", 12, words, 6);
-    else absorb_words(c, "aggregate", 9, words, 6);
+    if (ft) c.absorb_words("aggregate_ft", 12, words, 6);
+    else c.absorb_words("aggregate", 9, words, 6);
     const uint64_t n = (uint64_t)L * T;
     const uint64_t dims[3][3] = {{B, width, width}, {B, width, width}, {width, B, width}};
     for (int fam = 0; fam < 3; ++fam) {
@@ -446,6 +620,18 @@ VF_HD int aggregate(Ctx& c, const uint8_t* proof, size_t len) {
     if (rc) return (rc >= 100 ? 600 + rc - 100 : 500 + rc);
     if (r.at != len) return 103;
     return 0;
+}
+
+// 1/2 and 1/6 by Fermat (the host side; the device takes them from the context's constants)
+inline void host_inverses(Fr& inv2, Fr& inv6) {
+    uint32_t e[8];
+    for (int i = 0; i < 8; ++i) e[i] = frc::MOD[i];
+    e[0] = 0xffffffffu;   // r - 2: r[0] = 1 borrows from the next limb, which is 0xffffffff
+    e[1] -= 1u;
+    const Fr two = fr_add(fr_one(), fr_one());
+    const Fr six = fr_add(fr_add(two, two), two);
+    inv2 = fr_pow(two, e);
+    inv6 = fr_pow(six, e);
 }
 
 }  // namespace vf
