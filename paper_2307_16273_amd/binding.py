@@ -513,7 +513,8 @@ def hyrax_commit(ctx, key, x, blind=None):
     n = C.c_size_t(rows)
     bb = C.create_string_buffer(_fr_bytes(blind), 32 * rows) if blind is not None else None
     _check(load_library().hyrax_commit(ctx.handle, key.handle, x.handle, bb, out, C.byref(n)), "hyrax_commit", ctx)
-    return [out.raw[96 * k:96 * k + 96] for k in range(n.value)]
+    raw = out.raw   # one copy of the buffer, not one per row
+    return [raw[96 * k:96 * k + 96] for k in range(n.value)]
 
 
 def hyrax_open(ctx, x, blind, point):

@@ -227,14 +227,16 @@ FQ_HD Fq fq_mul12(const Fq& a) {   // b3 = 3 b = 12
     return fq_add(t, t);
 }
 
-// complete addition (Algorithm 7 of the reference above, a = 0)
-FQ_HD G1 g1_add(const G1& p, const G1& q) {
-    Fq t0 = fq_mul(p.X, q.X), t1 = fq_mul(p.Y, q.Y), t2 = fq_mul(p.Z, q.Z);
-    Fq t3 = fq_mul(fq_add(p.X, p.Y), fq_add(q.X, q.Y));
+// complete addition (Algorithm 7 of the reference above, a = 0); `mul` is the field product to use (the
+// kernels that add points in a loop pass an out-of-line one: twelve inlined products are 60 KB of code)
+template <class Mul>
+FQ_HD G1 g1_add_with(const G1& p, const G1& q, Mul mul) {
+    Fq t0 = mul(p.X, q.X), t1 = mul(p.Y, q.Y), t2 = mul(p.Z, q.Z);
+    Fq t3 = mul(fq_add(p.X, p.Y), fq_add(q.X, q.Y));
     t3 = fq_sub(t3, fq_add(t0, t1));
-    Fq t4 = fq_mul(fq_add(p.Y, p.Z), fq_add(q.Y, q.Z));
+    Fq t4 = mul(fq_add(p.Y, p.Z), fq_add(q.Y, q.Z));
     t4 = fq_sub(t4, fq_add(t1, t2));
-    Fq y3 = fq_mul(fq_add(p.X, p.Z), fq_add(q.X, q.Z));
+    Fq y3 = mul(fq_add(p.X, p.Z), fq_add(q.X, q.Z));
     y3 = fq_sub(y3, fq_add(t0, t2));
     Fq x3 = fq_add(t0, t0);
     t0 = fq_add(x3, t0);
@@ -242,14 +244,14 @@ FQ_HD G1 g1_add(const G1& p, const G1& q) {
     Fq z3 = fq_add(t1, t2);
     t1 = fq_sub(t1, t2);
     y3 = fq_mul12(y3);
-    x3 = fq_mul(t4, y3);
-    t2 = fq_mul(t3, t1);
+    x3 = mul(t4, y3);
+    t2 = mul(t3, t1);
     x3 = fq_sub(t2, x3);
-    y3 = fq_mul(y3, t0);
-    t1 = fq_mul(t1, z3);
+    y3 = mul(y3, t0);
+    t1 = mul(t1, z3);
     y3 = fq_add(t1, y3);
-    t0 = fq_mul(t0, t3);
-    z3 = fq_mul(z3, t4);
+    t0 = mul(t0, t3);
+    z3 = mul(z3, t4);
     z3 = fq_add(z3, t0);
     G1 r;
     r.X = x3;
@@ -257,6 +259,12 @@ FQ_HD G1 g1_add(const G1& p, const G1& q) {
     r.Z = z3;
     return r;
 }
+
+struct FqMulInline {
+    FQ_HD Fq operator()(const Fq& a, const Fq& b) const { return fq_mul(a, b); }
+};
+
+FQ_HD G1 g1_add(const G1& p, const G1& q) { return g1_add_with(p, q, FqMulInline()); }
 
 // doubling (Algorithm 9, a = 0)
 FQ_HD G1 g1_dbl(const G1& p) {

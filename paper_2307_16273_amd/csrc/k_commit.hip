@@ -13,7 +13,8 @@
 // runs over fixed-base window tables: for every generator the multiples d 2^(4k) G, d = 1..15, k < bits/4,
 // are built once with the key, and a commitment is a plain sum of one table entry per non-zero 4-bit digit
 // of |x| - no doublings and no buckets.  The blinding term rho H (rho a full field element) uses the same
-// kind of table with 64 windows.  All sums use the complete projective formulas of fq.cuh.
+// kind of table with 64 windows.  All sums use the complete projective formulas of fq.cuh: a row's sum may be
+// taken in any order.
 #include <string.h>
 #include <new>
 
@@ -23,7 +24,6 @@
 namespace {
 
 constexpr int CK_DIGITS = 15;        // table entries per window: d = 1..15
-constexpr int CK_CHUNK = 32;         // columns summed by one thread
 constexpr int CK_H_WINDOWS = 64;     // 4-bit windows of a 255-bit blinding scalar
 constexpr int CK_MAX_LABEL = 16;
 
@@ -122,44 +122,85 @@ __global__ __launch_bounds__(64) void k_ck_tables(const G1* gens, uint64_t ngens
     }
 }
 
-// part[row * nchunk + q] = sum over the columns of chunk q of x[row, c] G_c, from the window tables
-template <typename INT>
-__global__ __launch_bounds__(64) void k_commit_partial(const INT* x, uint64_t rows, uint64_t cols, uint64_t nchunk, int windows,
-                                                       const G1* table, G1* part) {
-    const uint64_t t = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
-    if (t >= rows * nchunk) return;
-    const uint64_t row = t / nchunk, q = t % nchunk;
-    const uint64_t c0 = q * CK_CHUNK, c1 = c0 + CK_CHUNK < cols ? c0 + CK_CHUNK : cols;
-    G1 acc = g1_identity();
-    for (uint64_t c = c0; c < c1; ++c) {
-        const INT s = x[row * cols + c];
-        const bool negative = s < 0;
-        uint64_t mag = negative ? (uint64_t)0 - (uint64_t)(int64_t)s : (uint64_t)s;
-        for (int k = 0; k < windows && mag != 0; ++k, mag >>= 4) {
-            const uint32_t d = (uint32_t)mag & 15u;
-            if (d == 0) continue;
-            G1 p = table[(c * (uint64_t)windows + k) * CK_DIGITS + d - 1];
-            if (negative) p.Y = fq_neg(p.Y);   // x = r - |x| as a field element: -|x| G
-            acc = g1_add(acc, p);
-        }
+// one copy of the 406-multiply-add field product for the kernels that add points in a loop
+__device__ __noinline__ Fq fq_mul_ni(Fq a, Fq b) { return fq_mul(a, b); }
+struct FqMulOutOfLine {
+    __device__ Fq operator()(const Fq& a, const Fq& b) const { return fq_mul_ni(a, b); }
+};
+__device__ inline G1 g1_add_ni(const G1& p, const G1& q) { return g1_add_with(p, q, FqMulOutOfLine()); }
+
+__device__ inline G1 g1_shfl_down(const G1& p, int off) {
+    G1 q;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        q.X.v[i] = __shfl_down(p.X.v[i], off, 64);
+        q.Y.v[i] = __shfl_down(p.Y.v[i], off, 64);
+        q.Z.v[i] = __shfl_down(p.Z.v[i], off, 64);
     }
-    part[t] = acc;
+    return q;
 }
 
-// row commitment = sum of its partial sums + rho_row H, written as affine bytes
-__global__ __launch_bounds__(64) void k_commit_finish(const G1* part, uint64_t rows, uint64_t nchunk, const uint32_t* rho_le,
-                                                      const G1* h_table, uint8_t* out) {
-    const uint64_t row = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
-    if (row >= rows) return;
-    G1 acc = part[row * nchunk];
-    for (uint64_t q = 1; q < nchunk; ++q) acc = g1_add(acc, part[row * nchunk + q]);
+// One wave per row: sums[row] = rho_row H + sum_c x[row, c] G_c (projective).  Lane l takes the columns
+// l, l + 64, .. and walks the non-zero 4-bit digits of their magnitudes as one stream: every trip of the loop
+// adds one table entry in every lane that still has a digit, whatever entry and window it belongs to, so lanes
+// do not wait for each other's zero digits.  Lane k also starts from window k of the blinding scalar.  The 64
+// partial sums are added by a shuffle tree.
+template <typename INT>
+__global__ __launch_bounds__(64) void k_commit_rows(const INT* x, uint64_t cols, int windows, const G1* table,
+                                                    const uint32_t* rho_le, const G1* h_table, G1* sums) {
+    static_assert(CK_H_WINDOWS == 64, "one lane per window of the blinding scalar");
+    const uint64_t row = blockIdx.x;
+    const int lane = threadIdx.x;
+    G1 acc = g1_identity();
     if (rho_le) {
-        for (int k = 0; k < CK_H_WINDOWS; ++k) {
-            const uint32_t d = (rho_le[row * 8 + (k >> 3)] >> (4 * (k & 7))) & 15u;
-            if (d) acc = g1_add(acc, h_table[k * CK_DIGITS + d - 1]);
+        const uint32_t d = (rho_le[row * 8 + (lane >> 3)] >> (4 * (lane & 7))) & 15u;
+        if (d) acc = h_table[lane * CK_DIGITS + d - 1];
+    }
+    const INT* xr = x + row * cols;
+    uint64_t c = (uint64_t)lane, mag = 0;
+    bool negative = false, loaded = false;
+    int k = 0;
+    for (;;) {
+        bool active = false;
+        while (c < cols) {   // this lane's next non-zero digit
+            if (!loaded) {
+                const INT s = xr[c];
+                negative = s < 0;
+                mag = negative ? (uint64_t)0 - (uint64_t)(int64_t)s : (uint64_t)s;
+                k = 0;
+                loaded = true;
+            }
+            if (mag == 0) {
+                loaded = false;
+                c += 64;
+                continue;
+            }
+            const int skip = (__ffsll((unsigned long long)mag) - 1) >> 2;
+            mag >>= 4 * skip;
+            k += skip;
+            active = true;
+            break;
+        }
+        if (__ballot(active) == 0) break;   // no lane has a digit left
+        if (active) {
+            const uint32_t d = (uint32_t)mag & 15u;
+            G1 p = table[(c * (uint64_t)windows + (uint64_t)k) * CK_DIGITS + d - 1];
+            if (negative) p.Y = fq_neg(p.Y);   // x = r - |x| as a field element: -|x| G
+            acc = g1_add_ni(acc, p);
+            mag >>= 4;
+            ++k;
         }
     }
-    g1_to_bytes(acc, out + row * 96);
+#pragma unroll 1
+    for (int off = 32; off >= 1; off >>= 1) acc = g1_add_ni(acc, g1_shfl_down(acc, off));
+    if (lane == 0) sums[row] = acc;
+}
+
+// affine bytes of the row sums: one inversion per row, one lane per row
+__global__ __launch_bounds__(64) void k_commit_affine(const G1* sums, uint64_t rows, uint8_t* out) {
+    const uint64_t row = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (row >= rows) return;
+    g1_to_bytes(sums[row], out + row * 96);
 }
 
 __global__ __launch_bounds__(64) void k_ck_export(const G1* gens, uint64_t first, uint64_t count, uint8_t* out) {
@@ -284,25 +325,21 @@ extern "C" int hyrax_commit(zkdl_ctx* ctx, const zkdl_commit_key* key, const zkd
         if (!below) return ZKDL_EINVAL;
     }
     ZK_HIP(ctx, hipSetDevice(ctx->device));
-    const uint64_t nchunk = (cols + CK_CHUNK - 1) / CK_CHUNK;
-    G1* part = (G1*)zk_alloc(ctx, sizeof(G1) * rows * nchunk);
+    G1* part = (G1*)zk_alloc(ctx, sizeof(G1) * rows);
     uint8_t* out_dev = (uint8_t*)zk_alloc(ctx, rows * 96);
     uint32_t* rho_dev = blind ? (uint32_t*)zk_alloc(ctx, rows * 32) : nullptr;
     int rc = (part && out_dev && (!blind || rho_dev)) ? ZKDL_OK : ZKDL_ENOMEM;
     hipError_t e = hipSuccess;
     if (rc == ZKDL_OK && blind) e = hipMemcpyAsync(rho_dev, blind, rows * 32, hipMemcpyHostToDevice, ctx->stream);
     if (rc == ZKDL_OK && e == hipSuccess) {
-        const uint64_t nt = rows * nchunk;
-        const unsigned grid = (unsigned)((nt + 63) / 64);
         // the key's tables have `windows` entries per generator whatever the tensor's width
         if (X->kind == TK_I32)
-            hipLaunchKernelGGL((k_commit_partial<int32_t>), dim3(grid), dim3(64), 0, ctx->stream, (const int32_t*)X->data, rows,
-                               cols, nchunk, key->windows, key->table, part);
+            hipLaunchKernelGGL((k_commit_rows<int32_t>), dim3((unsigned)rows), dim3(64), 0, ctx->stream,
+                               (const int32_t*)X->data, cols, key->windows, key->table, rho_dev, key->h_table, part);
         else
-            hipLaunchKernelGGL((k_commit_partial<int64_t>), dim3(grid), dim3(64), 0, ctx->stream, (const int64_t*)X->data, rows,
-                               cols, nchunk, key->windows, key->table, part);
-        hipLaunchKernelGGL(k_commit_finish, dim3((unsigned)((rows + 63) / 64)), dim3(64), 0, ctx->stream, part, rows, nchunk,
-                           rho_dev, key->h_table, out_dev);
+            hipLaunchKernelGGL((k_commit_rows<int64_t>), dim3((unsigned)rows), dim3(64), 0, ctx->stream,
+                               (const int64_t*)X->data, cols, key->windows, key->table, rho_dev, key->h_table, part);
+        hipLaunchKernelGGL(k_commit_affine, dim3((unsigned)((rows + 63) / 64)), dim3(64), 0, ctx->stream, part, rows, out_dev);
         e = hipMemcpyAsync(commitments_out, out_dev, rows * 96, hipMemcpyDeviceToHost, ctx->stream);
     }
     hipError_t e2 = hipStreamSynchronize(ctx->stream);
