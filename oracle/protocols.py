@@ -1104,3 +1104,77 @@ def aggregate_linked_verify(buf, ts):
         GZlast=(vn_w[:lt] + vi_w + h["u1"], gz_last),
         GW=(h["w"] + h["u0"] + h["u1"], pr["gradW"].claim0),
         aux=(zk["aux_claim"]["point"], zk["aux_claim"]["value"]))
+
+
+# --------------------------------------------------------------------------
+# proof of the parameter update (Sec. 5, Example FCNN, last item: "parameter updates, based on
+# the selected optimizer", a family of its own in Protocol zkdl).  The paper fixes no optimizer;
+# this build's reading: plain SGD on fixed-point weights with a power-of-two learning rate,
+#   W_next = W - U,  U = sround(G_W / 2^R)   (rounded to nearest, halves away from zero),
+# and since U = ReLU(rescale(G_W)) - ReLU(rescale(-G_W)) with zkReLU's own rescaling (round
+# half up), the rounding is proved by zkReLU's forward half on the stack Zu = [G_W; -G_W]:
+#   1. p drawn over the D entries; the prover claims a0 = Au~(0, p), a1 = Au~(1, p) for
+#      Au = ReLU(rescale(Zu)) = [U+; U-]; U~(p) = a0 - a1 is what the verifier compares with
+#      W~(p) - W_next~(p) (two openings of commitments, or claims of other sumchecks);
+#   2. the two claims on Au are merged into one, Au~(v_n, v) (stack_merge_prove on [2, D]);
+#   3. u_Z drawn over the 1 + log D variables of Zu; zkReLU at the given points u_A = (v_n, v)
+#      and u_Z proves that Au and Zu are what their bit decompositions say; its claim on Zu is
+#      Zu~(u_Z) = (1 - 2 u_Z[0]) G_W~(u_Z[1:]), a claim on the (committed) gradients.
+# --------------------------------------------------------------------------
+ZKUP_MAGIC = 0x50554B5A   # "ZKUP"
+
+
+def sround(g, r_bits):
+    """g / 2^r_bits rounded to the nearest integer, halves away from zero."""
+    g = int(g)
+    mag = (abs(g) + (1 << (r_bits - 1))) >> r_bits
+    return mag if g >= 0 else -mag
+
+
+def _sc_block_len(rounds, degree, n_finals):
+    return 16 + 32 + rounds * (degree + 1) * 32 + 32 * n_finals
+
+
+def update_prove(gw, q, r_bits, ts):
+    """gw: D = 2^k signed integers below 2^(q + r_bits - 1) in magnitude (q + r_bits <= 63).
+    Transcript: header "update" (log D, Q, R); draw p; the stack merge ("merge_stack" words
+    2, D, 2, its claims, coefficients and two sumchecks); draw u_Z; zkReLU at given points
+    (mode 2).  Proof: "ZKUP", log D, Q, R, 0, 0, 0, 0; the "ZKMS" block; the "ZKRL" block."""
+    d = len(gw)
+    ld = ilog2(d)
+    assert q + r_bits <= 63
+    ts.absorb_u32(b"update", [ld, q, r_bits])
+    p = ts.challenges_vec(ld)
+    zu = [int(g) for g in gw] + [-int(g) for g in gw]
+    wit = zkrelu_witness(zu, [0] * (2 * d), q, r_bits)
+    au = [int(a) for a in wit["A"]]
+    ms_buf, ms = stack_merge_prove(fr_array(au).reshape(2, d), 2, d, [[0] + p, [1] + p], ts, bind_statement=False)
+    u_a = ms["vn"] + ms["v"]
+    u_z = ts.challenges_vec(1 + ld)
+    zk_buf, zk = zkrelu_prove(zu, None, q, r_bits, ts, points=(u_z, u_a, u_z, u_z), bind_points=False)
+    assert zk["c_in"][1] == ms["outer"].finals[1], "zkReLU does not start from the merged claim on Au"
+    head = struct.pack("<IIIIIIII", ZKUP_MAGIC, ld, q, r_bits, 0, 0, 0, 0)
+    return head + ms_buf + zk_buf, dict(p=p, a=ms["claims"], u_a=u_a, u_z=u_z, merge=ms, zkrelu=zk)
+
+
+def update_verify(buf, ld, q, r_bits, ts):
+    """Replays the proof.  Returns the claims it leaves: u = (p, U~(p)), gw = (u_Z[1:], G_W~(u_Z[1:])),
+    aux = zkReLU's one claim on the bit tensor of Zu."""
+    magic, ld_, q_, r_, z0, z1, z2, z3 = struct.unpack_from("<IIIIIIII", buf, 0)
+    assert magic == ZKUP_MAGIC and (ld_, q_, r_) == (ld, q, r_bits) and z0 == z1 == z2 == z3 == 0
+    d = 1 << ld
+    ts.absorb_u32(b"update", [ld, q, r_bits])
+    p = ts.challenges_vec(ld)
+    ms_len = 16 + 64 + _sc_block_len(1 + ld, 2, 2) + _sc_block_len(1, 2, 2)
+    claims, pt, au_claim = stack_merge_verify(buf[32:32 + ms_len], 2, d, [[0] + p, [1] + p], ts, bind_statement=False)
+    u_z = ts.challenges_vec(1 + ld)
+    end, zk = zkrelu_verify(buf, ts, off=32 + ms_len, points=(u_z, pt, u_z, u_z))
+    assert end == len(buf), "trailing bytes"
+    li, q2, r2, has_ga = struct.unpack_from("<IIII", buf, 32 + ms_len + 4)
+    assert (li, q2, r2, has_ga) == (1 + ld, q, r_bits, 0)
+    assert zk["c_in"][1] == au_claim, "zkReLU's claim on Au is not the merged one"
+    assert zk["c_in"][2] == 0 and zk["c_in"][3] == 0
+    den = (1 - 2 * u_z[0]) % R_MOD
+    assert den != 0
+    gw_val = zk["c_in"][0] * pow(den, -1, R_MOD) % R_MOD
+    return dict(u=(p, (claims[0] - claims[1]) % R_MOD), gw=(u_z[1:], gw_val), aux=zk["aux_claim"])

@@ -168,6 +168,16 @@ def stack_merge_case():
             "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
 
 
+def update_case():
+    """Parameter update (Sec. 5, Example FCNN, last item): D = 4 gradients, Q = 5, R = 3, with both ties."""
+    gw = [77, -4, 4, -100]
+    ts = Transcript(17)
+    buf, info = P.update_prove(gw, 5, 3, ts)
+    return {"protocol": "update_prove", "cite": "Sec. 5, Example FCNN (parameter updates); Sec. 3.1, App. A", "seed": 17,
+            "GW": gw, "Q": 5, "R": 3,
+            "proof_hex": buf.hex(), "challenges": [hex(v) for v in ts.challenges], "digest_hex": ts.digest().hex()}
+
+
 if __name__ == "__main__":
     for name, fn in (("product_k3_d3", product_case), ("matmul_n2_2x4x2", matmul_case),
                      ("matmul_ft_n2_2x4x2", matmul_ft_case), ("matmul_general_n2_2x4x2", matmul_general_case),
@@ -176,7 +186,7 @@ if __name__ == "__main__":
                      ("aggregate_linked_l2_w4_b2_t2", aggregate_linked_case),
                      ("aggregate_ft_l2_w4_b2_t2", aggregate_ft_case),
                      ("reindex_n4_d8_k2", reindex_case), ("merge_d4_k3", merge_case),
-                     ("stack_merge_n4_d8_k2", stack_merge_case)):
+                     ("stack_merge_n4_d8_k2", stack_merge_case), ("update_d4_q5_r3", update_case)):
         with open(os.path.join(HERE, name + ".json"), "w") as f:
             json.dump(fn(), f, indent=1)
             f.write("\n")

@@ -31,6 +31,8 @@ def oracle_run(g):
     elif g["protocol"] == "sumcheck_matmul_general":
         buf = P.matmul_general_prove(fr_array(np.array(g["x0"])), g["x0_shape"], fr_array(np.array(g["x1"])), g["x1_shape"],
                                      fr_array(np.array(g["y"])), ts)[0]
+    elif g["protocol"] == "update_prove":
+        buf = P.update_prove(g["GW"], g["Q"], g["R"], ts)[0]
     elif g["protocol"] == "zkrelu_prove":
         buf = P.zkrelu_prove(g["Z"], g["GA"], g["Q"], g["R"], ts)[0]
     elif g["protocol"] == "zkrelu_prove_at":
@@ -69,7 +71,7 @@ def _without_repeats(points, drawn):
 
 NAMES = ["product_k3_d3", "matmul_n2_2x4x2", "matmul_ft_n2_2x4x2", "matmul_general_n2_2x4x2", "zkrelu_d4_q5_r3", "zkrelu_at_d4_q5_r3", "aggregate_l2_w4_b2_t2",
          "aggregate_linked_l2_w4_b2_t2", "aggregate_ft_l2_w4_b2_t2", "merge_d4_k3", "stack_merge_n4_d8_k2",
-         "reindex_n4_d8_k2"]
+         "reindex_n4_d8_k2", "update_d4_q5_r3"]
 
 
 @pytest.mark.parametrize("name", NAMES)
@@ -114,6 +116,10 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
         got = lib.claims_merge_prove(ctx, x, pts, tr, stack=stack)
     elif g["protocol"] == "zkrelu_prove":
         got = lib.zkrelu_prove(ctx, np.array(g["Z"], dtype=np.int64), np.array(g["GA"], dtype=np.int64), tr, g["Q"], g["R"])
+    elif g["protocol"] == "update_prove":
+        if not hasattr(lib, "update_prove"):
+            pytest.skip("update_prove is not in the library yet")
+        got = lib.update_prove(ctx, np.array(g["GW"], dtype=np.int64), tr, g["Q"], g["R"])
     elif g["protocol"] == "zkrelu_prove_at":
         pts = [[int(v, 16) for v in pt] for pt in g["points"]]
         given = [hex(v) for pt in pts for v in pt]
@@ -126,7 +132,7 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
             dw[k] = torch.from_numpy(np.ascontiguousarray(wit[k])).cuda()
         got = lib.aggregate_prove(ctx, dw, tr, linked=g["protocol"] == "aggregate_prove_linked",
                                   ft=g["protocol"] == "aggregate_prove_ft")
-    if g["protocol"] == "aggregate_prove_linked":
+    if g["protocol"] in ("aggregate_prove_linked", "update_prove"):
         # the four points given to zkReLU are not draws: they come back in front of its own
         drawn = {int(v, 16) for v in g["challenges"]}
         assert [v for v in got["points"] if v not in drawn] == []
