@@ -60,7 +60,7 @@
  *              finals aux~(k*,v,w*), E~(k*,w*))
  *   aggregate: "ZKAG", L, B, width, T', Q, R, 0, SC block forward, SC block
  *              gradA, SC block gradW, zkReLU proof
- *   "ZKGA" (sumcheck_matmul_general), "ZKSF" (sumcheck_matmul_ft), "ZKRI" (reindex_prove), "ZKMG"
+ *   "ZKUP" (update_prove), "ZKGA" (sumcheck_matmul_general), "ZKSF" (sumcheck_matmul_ft), "ZKRI" (reindex_prove), "ZKMG"
  *   (claims_merge_prove), "ZKMS" (claims_merge_stack_prove) and "ZKAL"
  *   (aggregate_prove_linked) are laid out at their declarations below.
  * points_out also repeats, in front of the draws they precede, points that a
@@ -359,7 +359,8 @@ typedef enum {
     ZKDL_T_W_NEXT = 10,  /* W with slot (t,l) <- slot (t,l+1), zero in last-layer slots; point in W's (in, out) order */
     ZKDL_T_AUX = 11,     /* aux [2, N B width, J]: the bit decompositions of Zr and GA */
     ZKDL_T_Z_LAST = 12,  /* Z of the last layer [T',B,width] */
-    ZKDL_T_GZ_LAST = 13  /* GZ of the last layer [T',B,width] */
+    ZKDL_T_GZ_LAST = 13, /* GZ of the last layer [T',B,width] */
+    ZKDL_T_U = 14        /* update_prove: U = G_W / 2^R rounded to nearest, W_next = W - U */
 } zkdl_claim_tensor;
 #define ZKDL_CLAIM_MAX_SEGS 4
 typedef struct {
@@ -384,6 +385,29 @@ typedef struct {
 int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr, uint8_t* proof,
                     size_t* proof_len, zkdl_fr* points_out, size_t* npoints, zkdl_claim* claims_out,
                     size_t* nclaims);
+
+/* update_prove: the parameter update of a training step (Sec. 5, Example FCNN, the last item of its list:
+ * "parameter updates, based on the selected optimizer", a family of its own in Protocol zkdl).  The paper fixes
+ * no optimizer; this entry point proves plain SGD on fixed-point weights with a power-of-two learning rate,
+ *   W_next = W - U,   U = G_W / 2^R rounded to the nearest integer, halves away from zero,
+ * for the D = 2^k entries of a gradient stack G_W (int64, host or device; |G_W| < 2^(Q+R-1), Q + R <= 63, else
+ * ZKDL_ERANGE / ZKDL_EINVAL).  U = ReLU(rescale(G_W)) - ReLU(rescale(-G_W)) with zkReLU's rescaling (Sec. 3.1),
+ * so the rounding is proved by zkReLU's forward half (App. A) on the stack Zu = [G_W; -G_W]:
+ *   1. p is drawn over the D entries; the prover claims a0 = Au~(0,p), a1 = Au~(1,p), Au = ReLU(rescale(Zu));
+ *      U~(p) = a0 - a1 is the value the verifier compares with W~(p) - W_next~(p);
+ *   2. the two claims on Au are merged into one, Au~(v_n, v) (as claims_merge_stack_prove on [2, D]);
+ *   3. u_Z is drawn over the 1 + log2 D variables of Zu and zkReLU runs at the given points u_A = (v_n, v),
+ *      u_Z (as zkrelu_prove_at inside a larger proof: mode 2); its claim on Zu gives
+ *      G_W~(u_Z[1:]) = Zu~(u_Z) / (1 - 2 u_Z[0]).
+ * claims_out (ZKDL_UPDATE_NCLAIMS entries, may be NULL): U at p, GW at u_Z[1:], AUX (the bits of Zu) at zkReLU's
+ * merged point; segments index points_out as in aggregate_prove.  points_out: every challenge in draw order,
+ * with the three copied points of zkReLU (u_A, and u_Z twice for the unused backward side) after u_Z.
+ * Transcript: header "update" (log2 D, Q, R); draw p; "merge_stack" (2, D, 2) and the merge; draw u_Z; zkReLU.
+ * Proof: "ZKUP", log2 D, Q, R, 0, 0, 0, 0; a "ZKMS" block; a "ZKRL" block. */
+#define ZKDL_UPDATE_NCLAIMS 3
+int update_prove(zkdl_ctx* ctx, const int64_t* GW, uint64_t D, int Q, int R, int src_on_device, zkdl_transcript* tr,
+                 uint8_t* proof, size_t* proof_len, zkdl_fr* points_out, size_t* npoints, zkdl_claim* claims_out,
+                 size_t* nclaims);
 
 /* aggregate_prove_ft: aggregate_prove with the three matrix-product families in the optimized aggregated
  * form of App. B (Protocol tensor-op-aggr-optimized), each as in sumcheck_matmul_ft: the log2 N stack

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "zkdl_transcript_challenge", "zkdl_transcript_digest",
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
-    "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_matmul_general", "sumcheck_hadamard",
+    "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_matmul_general", "update_prove", "sumcheck_hadamard",
     "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "aggregate_prove_ft", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read", "zkdl_selfbench",
     "zkdl_commit_key_create", "zkdl_commit_key_destroy", "zkdl_commit_key_generators", "hyrax_commit", "hyrax_open",
@@ -49,7 +49,7 @@ class Claim(C.Structure):
 
 
 CLAIM_TENSORS = ["A", "W", "GZ", "Z", "ZR", "GA", "GW", "A_RELU", "GZ_RELU", "GZ_NEXT", "W_NEXT", "AUX",
-                 "Z_LAST", "GZ_LAST"]
+                 "Z_LAST", "GZ_LAST", "U"]
 
 
 def library_path():
@@ -91,6 +91,7 @@ def load_library():
         "zkrelu_prove": [vp, vp, vp, u64, i, i, i, vp, vp, psz, vp, vp, psz],
         "zkrelu_prove_at": [vp, vp, vp, u64, i, i, i, vp, vp, vp, psz, vp, vp, psz],
         "aggregate_prove": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz, vp, psz],
+        "update_prove": [vp, vp, u64, i, i, i, vp, vp, psz, vp, psz, vp, psz],
         "aggregate_prove_linked": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz, vp, psz],
         "aggregate_prove_ft": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
         "zkdl_host_fr_mul": [vp, vp, vp], "zkdl_selfcheck_constants": [],
@@ -426,6 +427,27 @@ def zkrelu_prove(ctx, z, ga, tr, q=32, r=16, points=None):
                                        C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
            "zkrelu_prove", ctx)
     return o.result()
+
+
+def update_prove(ctx, gw, tr, q=32, r=30):
+    """gw: int64 numpy array (host) or int64 CUDA tensor, a power of two of entries.  Returns proof, points and
+    claims_left (U at p, GW, AUX)."""
+    gp, g_dev, gc, keep = _src_pointer(gw)
+    assert gc == ZKDL_I64
+    d = int(np.prod(gw.shape))
+    o = _Outputs(0)
+    claims = (Claim * 4)()
+    nclaims = C.c_size_t(4)
+    _check(load_library().update_prove(ctx.handle, gp, d, q, r, g_dev, tr.handle, o.proof, C.byref(o.proof_len),
+                                       o.points, C.byref(o.npoints), claims, C.byref(nclaims)), "update_prove", ctx)
+    out = o.result()
+    pts = out["points"]
+    out["claims_left"] = [
+        dict(tensor=CLAIM_TENSORS[c.tensor],
+             point=[x for s in range(c.nseg) for x in pts[c.seg_off[s]:c.seg_off[s] + c.seg_len[s]]],
+             value=int.from_bytes(bytes(c.value), "little"))
+        for c in claims[:nclaims.value]]
+    return out
 
 
 def aggregate_prove(ctx, wit, tr, linked=False, ft=False):

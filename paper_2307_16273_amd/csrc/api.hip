@@ -1490,6 +1490,25 @@ extern "C" int zkrelu_prove_at(zkdl_ctx* ctx, const int64_t* Z, const int64_t* G
                        npoints);
 }
 
+// ---- proof of the parameter update ------------------------------------------------------------
+static const uint32_t ZKUP_MAGIC = 0x50554B5Au;
+static const uint32_t ZKMS_MAGIC_UP = 0x534D4B5Au;
+
+// zu = [g; -g], au = ReLU(rescale(zu)) with zkReLU's rescaling (round half up): au = [U+; U-]
+__global__ __launch_bounds__(ZK_BLOCK) void k_update_witness(const int64_t* g, uint64_t D, int r_bits, int64_t* zu,
+                                                             int64_t* au) {
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < D; i += (uint64_t)gridDim.x * blockDim.x) {
+        const int64_t x = g[i];
+        const int64_t nx = (int64_t)((uint64_t)0 - (uint64_t)x);
+        zu[i] = x;
+        zu[D + i] = nx;
+        const int64_t up = (x >> r_bits) + ((x >> (r_bits - 1)) & 1);
+        const int64_t un = (nx >> r_bits) + ((nx >> (r_bits - 1)) & 1);
+        au[i] = up > 0 ? up : 0;
+        au[D + i] = un > 0 ? un : 0;
+    }
+}
+
 // ---- the list of claims a window leaves (host side, after the call has ended) ----
 struct ClaimList {
     zkdl_claim* out;
@@ -1533,6 +1552,117 @@ static Fr fr_from_le32(const uint8_t* p) {
     Fr x;
     memcpy(x.v, p, 32);
     return fr_to_mont(x);
+}
+
+extern "C" int update_prove(zkdl_ctx* ctx, const int64_t* GW, uint64_t D, int Q, int R, int src_on_device,
+                            zkdl_transcript* tr, uint8_t* proof, size_t* proof_len, zkdl_fr* points_out, size_t* npoints,
+                            zkdl_claim* claims_out, size_t* nclaims) {
+    if (!ctx || !GW || !tr) return ZKDL_EINVAL;
+    if (!is_pow2(D) || D > ((uint64_t)1 << 29) || Q < 1 || R < 1 || Q + R > 63) return ZKDL_EINVAL;
+    int rc = claims_capacity(claims_out, nclaims, points_out, ZKDL_UPDATE_NCLAIMS);
+    if (rc != ZKDL_OK) return rc;
+    const int ld = ilog2_u64(D), li = ld + 1;
+    int lj = 0;
+    while ((1 << lj) < Q + R) ++lj;
+    rc = call_begin(ctx, tr);
+    if (rc != ZKDL_OK) return rc;
+    // the coordinates 0 and 1 of the stack axis of Au, as canonical bytes
+    uint8_t consts[64] = {};
+    consts[32] = 1;
+    void *d_const = nullptr, *gs = nullptr;
+    rc = upload_bytes(ctx, consts, sizeof consts, &d_const);
+    const int64_t* gd = GW;
+    if (rc == ZKDL_OK && !src_on_device) {
+        rc = stage_ints(ctx, GW, D, &gs);
+        gd = (const int64_t*)gs;
+    }
+    int64_t* zu = (int64_t*)zk_alloc(ctx, 2 * D * 8);
+    int64_t* au = (int64_t*)zk_alloc(ctx, 2 * D * 8);
+    if (rc == ZKDL_OK && (!zu || !au)) rc = ZKDL_ENOMEM;
+    std::vector<void*> keep;
+    int cp = 0, c_ms = 0, cz = 0;
+    size_t p_ms = 0, pz = 0, pz_end = 0;
+    if (rc == ZKDL_OK) {
+        const uint64_t blocks = (D + ZK_BLOCK - 1) / ZK_BLOCK;
+        hipLaunchKernelGGL(k_update_witness, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(ZK_BLOCK), 0, ctx->stream,
+                           gd, D, R, zu, au);
+        uint32_t hw[3] = {(uint32_t)ld, (uint32_t)Q, (uint32_t)R};
+        zk_absorb_words(ctx, "update", hw, 3);
+        uint32_t hdr[8] = {ZKUP_MAGIC, hw[0], hw[1], hw[2], 0, 0, 0, 0};
+        zk_write_proof_words(ctx, hdr, 8);
+        cp = ctx->n_chal;
+        zk_launch_draw(ctx, cp, ld);
+        ctx->n_chal += ld;
+        // the two claims Au~(0, p), Au~(1, p) become one: a merge on the stack [2, D]
+        const int at0 = ZK_MAX_CHAL - ZK_CHAL_SET_MAX, at1 = at0 + ZK_CHAL_SET_MAX / 2;
+        ChalIdx pi = {};
+        for (int i = 0; i < ld; ++i) pi.v[i] = (int16_t)(cp + i);
+        zk_launch_chal_set(ctx, at0, 1, (const uint8_t*)d_const, nullptr);
+        zk_launch_chal_set(ctx, at1, 1, (const uint8_t*)d_const + 32, nullptr);
+        if (ld > 0) {
+            zk_launch_chal_set(ctx, at0 + 1, ld, nullptr, &pi);
+            zk_launch_chal_set(ctx, at1 + 1, ld, nullptr, &pi);
+        }
+        uint32_t hw3[3] = {2, (uint32_t)D, 2};
+        zk_absorb_words(ctx, "merge_stack", hw3, 3);
+        uint32_t mh[4] = {ZKMS_MAGIC_UP, 2, (uint32_t)D, 2};
+        zk_write_proof_words(ctx, mh, 4);
+        p_ms = ctx->proof_len;
+        c_ms = ctx->n_chal;
+        StackMergeJob job = {};
+        job.K = 2;
+        job.point[0] = ctx->dev->chal + at0;
+        job.point[1] = ctx->dev->chal + at1;
+        job.kind = TK_I64;
+        job.X = au;
+        job.N = 2;
+        job.rows = (uint64_t)1 << (ld / 2);
+        job.cols = (uint64_t)1 << (ld - ld / 2);
+        rc = zk_stack_merge(ctx, job, keep);
+    }
+    if (rc == ZKDL_OK && ctx->n_chal + 4 * li > ZK_MAX_CHAL - ZK_CHAL_SET_MAX) rc = ZKDL_EINVAL;
+    if (rc == ZKDL_OK) {
+        // zkReLU on Zu = [G_W; -G_W]: u_Z drawn where the first given point stands, u_A = the merged point
+        // (v_n, v), the two backward points (unused: there is no gradient side) copies of u_Z
+        const int c_v = c_ms + 2 + 1, c_vn = c_v + ld;   // merge: 2 coefficients, rho, v (ld), then v_n
+        cz = ctx->n_chal;
+        zk_launch_draw(ctx, cz, li);
+        ChalIdx idx = {};
+        int at = 0;
+        idx.v[at++] = (int16_t)c_vn;
+        for (int i = 0; i < ld; ++i) idx.v[at++] = (int16_t)(c_v + i);
+        for (int rep = 0; rep < 2; ++rep)
+            for (int i = 0; i < li; ++i) idx.v[at++] = (int16_t)(cz + i);
+        zk_launch_chal_set(ctx, cz + li, 3 * li, nullptr, &idx);
+        pz = ctx->proof_len;
+        rc = enqueue_zkrelu(ctx, zu, nullptr, 2 * D, Q, R, 2, nullptr);
+        pz_end = ctx->proof_len;
+    }
+    int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
+    if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims_out) {
+        const uint8_t* sp = staged_proof(ctx);
+        const uint8_t* chal_le = ((const DevState*)ctx->host_stage)->chal_le;
+        ClaimList cl = {claims_out, 0, sp};
+        // U~(p) = Au~(0, p) - Au~(1, p)
+        const Fr u = fr_from_mont(fr_sub(fr_from_le32(sp + p_ms), fr_from_le32(sp + p_ms + 32)));
+        cl.add(ZKDL_T_U, {{cp, ld}}, (const uint8_t*)u.v);
+        // Zu~(u_Z) = (1 - 2 u_Z[0]) G_W~(u_Z[1:])
+        const Fr u0 = fr_from_le32(chal_le + 32 * (size_t)cz);
+        const Fr den = fr_sub(fr_one(), fr_add(u0, u0));
+        const Fr zero = fr_zero();
+        const Fr g = fr_eq(den, zero) ? zero : fr_mul(fr_from_le32(sp + pz + 32), host_inverse(den));
+        const Fr gp = fr_from_mont(g);
+        cl.add(ZKDL_T_GW, {{cz + 1, ld}}, (const uint8_t*)gp.v);
+        const int c_v = cz + 5 * li + lj + 2, c_vm = c_v + li + lj + 3;
+        cl.add_at(ZKDL_T_AUX, {{c_vm, 1}, {c_v, li}, {c_vm + 1, lj}}, pz_end - 64);
+        *nclaims = cl.n;
+    }
+    for (void* p : keep) zk_free(ctx, p);
+    zk_free(ctx, zu);
+    zk_free(ctx, au);
+    zk_free(ctx, gs);
+    zk_free(ctx, d_const);
+    return rc != ZKDL_OK ? rc : rc2;
 }
 
 extern "C" int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* tr,

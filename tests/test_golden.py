@@ -117,8 +117,6 @@ def test_library_reproduces_stored_proofs(lib, ctx, name):
     elif g["protocol"] == "zkrelu_prove":
         got = lib.zkrelu_prove(ctx, np.array(g["Z"], dtype=np.int64), np.array(g["GA"], dtype=np.int64), tr, g["Q"], g["R"])
     elif g["protocol"] == "update_prove":
-        if not hasattr(lib, "update_prove"):
-            pytest.skip("update_prove is not in the library yet")
         got = lib.update_prove(ctx, np.array(g["GW"], dtype=np.int64), tr, g["Q"], g["R"])
     elif g["protocol"] == "zkrelu_prove_at":
         pts = [[int(v, 16) for v in pt] for pt in g["points"]]

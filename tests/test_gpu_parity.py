@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from oracle.field import R_MOD, fr_array, fr_array_from_le, array_to_le
-from oracle.mle import partial_eval
+from oracle.mle import partial_eval, mle_eval as P_mle_eval
 from oracle import protocols as P
 from oracle.transcript import Transcript as OracleTranscript
 from workloads import uniform_fr_limbs, fcnn_window, fc_relu_layer, CONFIG_SEED
@@ -718,6 +718,143 @@ def test_zkrelu_device_inputs_and_range_error(lib, ctx):
         assert tr.digest() == before        # a failed call leaves the transcript untouched
         with pytest.raises(ValueError):
             P.zkrelu_prove(z2.tolist(), g2.tolist(), 32, 16, OracleTranscript(2))
+
+
+def _update_gradients(seed, d, q, r):
+    rng = np.random.default_rng(seed)
+    lim = 1 << (q + r - 1)
+    g = rng.integers(-lim + 1, lim, d, dtype=np.int64)
+    half = 1 << (r - 1)
+    for k, v in enumerate([half, -half, 3 * half, -3 * half, 0, lim - 1, -lim + 1, 1, -1]):
+        if k < d:
+            g[k] = v
+    return g
+
+
+def _drawn_only(points, drawn):
+    """The library repeats the points it hands to zkReLU; the drawn challenges remain, in order."""
+    out, k = [], 0
+    for v in points:
+        if k < len(drawn) and v == drawn[k]:
+            out.append(v)
+            k += 1
+    return out
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d,q,r,on_device", [
+    (1, 5, 3, False),            # one entry: no coordinates in p
+    (2, 4, 4, False),            # Q + R a power of two
+    (8, 6, 4, True),
+    (64, 10, 6, False),
+    (256, 32, 30, True),         # the widths of a real step: learning rate 2^-14 on 16 fractional bits
+    (1024, 33, 30, False),       # Q + R = 63, the widest allowed
+])
+def test_update_prove(lib, ctx, d, q, r, on_device):
+    """The proof of the parameter update: proof bytes, challenges, transcript and the three claims against
+    the oracle, and the update claim against the definition of rounding to nearest."""
+    import torch
+    say(f"update_prove D={d} Q={q} R={r} device={on_device}")
+    g = _update_gradients(d * 10 + q, d, q, r)
+    src = torch.from_numpy(g).cuda() if on_device else g
+    tr = lib.Transcript(31)
+    got = lib.update_prove(ctx, src, tr, q, r)
+    ots = OracleTranscript(31)
+    buf, info = P.update_prove([int(x) for x in g], q, r, ots)
+    assert got["proof"] == buf
+    assert tr.digest() == ots.digest()
+    assert _drawn_only(got["points"], ots.challenges) == ots.challenges
+    ld = d.bit_length() - 1
+    out = P.update_verify(got["proof"], ld, q, r, OracleTranscript(31))
+    left = {c["tensor"]: c for c in got["claims_left"]}
+    assert [c["tensor"] for c in got["claims_left"]] == ["U", "GW", "AUX"]
+    assert left["U"]["point"] == out["u"][0] and left["U"]["value"] == out["u"][1]
+    assert left["GW"]["point"] == out["gw"][0] and left["GW"]["value"] == out["gw"][1]
+    assert left["AUX"]["point"] == out["aux"]["point"] and left["AUX"]["value"] == out["aux"]["value"]
+    u = [P.sround(int(x), r) for x in g]
+    assert left["U"]["value"] == P_mle_eval(fr_array(u), left["U"]["point"])
+
+
+@pytest.mark.gpu
+def test_update_prove_range_and_arguments(lib, ctx):
+    say("update_prove error paths")
+    tr = lib.Transcript(2)
+    before = tr.digest()
+    for g, q, r in ((np.array([1 << 9, 0], dtype=np.int64), 5, 5),        # 2^(Q+R-1) itself
+                    (np.array([-(1 << 9), 0], dtype=np.int64), 5, 5),     # in range, its negation is not
+                    (np.array([1, 2, 3], dtype=np.int64), 5, 5),          # not a power of two
+                    (np.array([1, 2], dtype=np.int64), 34, 30)):          # Q + R = 64
+        with pytest.raises(lib.ZkdlError):
+            lib.update_prove(ctx, g, tr, q, r)
+        assert tr.digest() == before
+
+
+@pytest.mark.gpu
+def test_update_prove_weight_stack_by_properties(lib, ctx):
+    """A stack of 2^20 gradients (16 layers of 256 x 256): the oracle's verifier replays the proof, and the three
+    claims it leaves are evaluated directly from the integers."""
+    import torch
+    say("update_prove on 2^20 gradients")
+    d, q, r = 1 << 20, 32, 30
+    rng = np.random.default_rng(CONFIG_SEED + 70)
+    g = rng.integers(-(1 << 44), 1 << 44, d, dtype=np.int64)
+    g[:4] = [1 << 29, -(1 << 29), 3 << 29, -(3 << 29)]
+    tr = lib.Transcript(8)
+    got = lib.update_prove(ctx, torch.from_numpy(g).cuda(), tr, q, r)
+    tv = OracleTranscript(8)
+    out = P.update_verify(got["proof"], 20, q, r, tv)
+    assert tv.digest() == tr.digest()
+    left = {c["tensor"]: c for c in got["claims_left"]}
+    half = 1 << (r - 1)
+    mag = (np.abs(g) + half) >> r
+    u = np.where(g >= 0, mag, -mag)
+    assert left["U"]["value"] == out["u"][1] == _int_mle(u, left["U"]["point"])
+    assert left["GW"]["value"] == out["gw"][1] == _int_mle(g, left["GW"]["point"])
+    # the gradient stack of the 8 x 1024^2 network (2^23 entries, 2^24 rows of 62 bits in zkReLU): the oracle's
+    # verifier, ending in the library's transcript state
+    say("update_prove on 2^23 gradients")
+    d = 1 << 23
+    g = rng.integers(-(1 << 44), 1 << 44, d, dtype=np.int64)
+    tr = lib.Transcript(9)
+    got = lib.update_prove(ctx, torch.from_numpy(g).cuda(), tr, q, r)
+    tv = OracleTranscript(9)
+    out = P.update_verify(got["proof"], 23, q, r, tv)
+    assert tv.digest() == tr.digest()
+    left = {c["tensor"]: c for c in got["claims_left"]}
+    assert left["U"]["value"] == out["u"][1] and left["GW"]["value"] == out["gw"][1]
+    assert left["AUX"]["value"] == out["aux"]["value"] and left["AUX"]["point"] == out["aux"]["point"]
+
+
+@pytest.mark.gpu
+def test_update_prove_on_a_generated_window(lib, ctx):
+    """The weights of consecutive steps of a seeded window differ by the update that the proof speaks of:
+    U~(p) from the library equals (W_t - W_{t+1})~(p) of the window's own weight stack."""
+    import torch
+    say("update_prove on the steps of a window")
+    layers, width, batch, steps = 4, 32, 8, 3
+    wit = fcnn_window(CONFIG_SEED + 92, n_layers=layers, width=width, batch=batch, steps=steps)
+    r_bits = 16 + 8 + 3
+    for t in range(steps - 1):
+        a = wit["A"][t * layers:(t + 1) * layers].astype(np.int64)
+        gz = wit["GZ"][t * layers:(t + 1) * layers].astype(np.int64)
+        gw = np.einsum("lbi,lbo->lio", a, gz).reshape(-1)
+        w0 = wit["W"][t * layers:(t + 1) * layers].astype(np.int64).reshape(-1)
+        w1 = wit["W"][(t + 1) * layers:(t + 2) * layers].astype(np.int64).reshape(-1)
+        assert np.any(w0 != w1)
+        got = lib.update_prove(ctx, torch.from_numpy(gw).cuda(), lib.Transcript(50 + t), 32, r_bits)
+        left = {c["tensor"]: c for c in got["claims_left"]}
+        assert left["U"]["value"] == _int_mle(w0 - w1, left["U"]["point"])
+        assert left["GW"]["value"] == _int_mle(gw, left["GW"]["point"])
+        P.update_verify(got["proof"], len(gw).bit_length() - 1, 32, r_bits, OracleTranscript(50 + t))
+
+
+def _int_mle(values, point):
+    """MLE of a vector of Python-int-sized integers at a point, folding one coordinate at a time."""
+    cur = np.array([int(v) % R_MOD for v in values], dtype=object)
+    for c in point:
+        half = len(cur) // 2
+        cur = (cur[:half] + c * (cur[half:] - cur[:half])) % R_MOD
+    return int(cur[0])
 
 
 def to_cuda_witness(wit):

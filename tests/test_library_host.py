@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b([a-z_0-9]+)\s*\(", header)) - {"defined"}
     declared = {d for d in declared if d.startswith(("zkdl_", "fr_", "mle_", "sumcheck_", "zkrelu_",
-                                                       "aggregate_", "reindex_", "claims_", "hyrax_"))}
+                                                       "aggregate_", "reindex_", "claims_", "hyrax_", "update_"))}
     assert declared == set(zk.EXPORTED_SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name

@@ -7,6 +7,7 @@ from oracle.field import R_MOD, fr_array
 from oracle.mle import mle_eval, ilog2
 from oracle import protocols as P
 from oracle.transcript import Transcript
+from workloads import fcnn_window, CONFIG_SEED
 
 
 def nearest_away(g, r_bits):
@@ -118,3 +119,27 @@ def test_update_rejects_out_of_range_and_tampering():
         P.update_verify(buf, 2, 5, 3, Transcript(4))             # another transcript
     with pytest.raises(AssertionError):
         P.update_verify(buf + b"\x00" * 32, 2, 5, 3, Transcript(2))
+
+
+def window_gradients(wit, t):
+    """G_W = A^T G_Z of every layer of step t, and the weights before and after the step."""
+    n_layers = wit["L"]
+    a = wit["A"][t * n_layers:(t + 1) * n_layers].astype(np.int64)
+    gz = wit["GZ"][t * n_layers:(t + 1) * n_layers].astype(np.int64)
+    gw = np.einsum("lbi,lbo->lio", a, gz)
+    return gw, wit["W"][t * n_layers:(t + 1) * n_layers].astype(np.int64), \
+        wit["W"][(t + 1) * n_layers:(t + 2) * n_layers].astype(np.int64)
+
+
+def test_update_of_a_generated_window():
+    # the weights of consecutive steps of a seeded window differ by the update the proof speaks of
+    wit = fcnn_window(CONFIG_SEED + 91, n_layers=2, width=4, batch=2, steps=3)
+    r_bits = 16 + 8 + 1          # the generator's learning-rate shift for batch 2
+    for t in range(2):
+        gw, w0, w1 = window_gradients(wit, t)
+        g = [int(x) for x in gw.reshape(-1)]
+        buf, _ = P.update_prove(g, 32, r_bits, Transcript(40 + t))
+        out = P.update_verify(buf, ilog2(len(g)), 32, r_bits, Transcript(40 + t))
+        p, u_val = out["u"]
+        diff = [int(x) for x in (w0 - w1).reshape(-1)]
+        assert u_val == mle_eval(fr_array(diff), p)

@@ -32,6 +32,12 @@ def _rescale(x, bits=SCALE_BITS):
     return (x + (1 << (bits - 1))) >> bits
 
 
+def _rescale_nearest(x, bits):
+    """x / 2^bits to the nearest integer, halves away from zero (the rule of the weight update)."""
+    mag = (np.abs(x) + (1 << (bits - 1))) >> bits
+    return np.where(x >= 0, mag, -mag)
+
+
 def fc_relu_layer(seed, batch=16, width=256):
     """One FC layer + ReLU: X [batch,width] ~ U[0,1), W [width,width] ~ N(0, 2/width),
     both quantised at 2^16; Z = X W as 48-bit integers."""
@@ -48,7 +54,8 @@ def fcnn_window(seed, n_layers, width, batch, steps=1, lr_shift=None, q_bits=32,
 
     Step t draws its batch A^(0) ~ U[0,1) and output gradient dL/dY ~ N(0, 1e-2)
     (variance) from default_rng(seed + 1 + t); weights ~ N(0, 2/width) from
-    default_rng(seed) before step 0.  Between steps W <- W - rescale(G_W, 16 + lr_shift);
+    default_rng(seed) before step 0.  Between steps W <- W - G_W / 2^(16 + lr_shift) rounded to nearest
+    (halves away from zero);
     by default lr_shift = 8 + log2(batch): learning rate 2^-8 on the batch-mean gradient
     (with the summed gradient the random output gradients make the weights, and then the
     activations, leave the 32-bit range within a few steps).
@@ -94,7 +101,7 @@ def fcnn_window(seed, n_layers, width, batch, steps=1, lr_shift=None, q_bits=32,
             k = t * n_layers + l
             gz_st[k] = g_z
             g_w = _exact_matmul(a_st[k].T, g_z)
-            new_weights[l] = weights[l] - _rescale(g_w, SCALE_BITS + lr_shift)
+            new_weights[l] = weights[l] - _rescale_nearest(g_w, SCALE_BITS + lr_shift)
             assert np.abs(new_weights[l]).max() < (1 << 31)
             if l > 0:
                 g_a = _exact_matmul(g_z, weights[l].T)
