@@ -1926,4 +1926,73 @@ int zko_stack_merge_prove(const uint8_t* x, uint64_t n, uint64_t d, int K, const
     return wb.len <= wb.cap ? 0 : ZKO_ESMALL;
 }
 
+/* Proof of the parameter update (Sec. 5, Example FCNN, last item; the rounding by zkReLU, Sec. 3.1 and App. A),
+ * the steps of the first tier's update_prove in the same order: header, p, Au = ReLU(rescale([G; -G])), the
+ * merge of the two claims Au~(0, p), Au~(1, p) on the stack [2, D], u_Z, zkReLU at the given points. */
+int zko_update_prove(const int64_t* gw, uint64_t D, int q, int rb, zko_ts* ts, uint8_t* proof, uint64_t cap,
+                     uint64_t* proof_len) {
+    init_mu();
+    const int ld = ilog2_u64(D);
+    if (ld < 0 || ld > 38 || !gw || !ts || q < 1 || rb < 1 || q + rb > 63) return ZKO_EARG;
+    const int li = ld + 1;
+    const int64_t lim = (int64_t)1 << (q + rb - 1), half = (int64_t)1 << (rb - 1);
+    uint32_t hdr[3] = {(uint32_t)ld, (uint32_t)q, (uint32_t)rb};
+    ts_absorb_u32(ts, "update", hdr, 3);
+    fe p[40];
+    ts_draw(ts, ld, p);
+    int64_t* zu = (int64_t*)malloc(sizeof(int64_t) * 2 * D);
+    fe* au = (fe*)malloc(sizeof(fe) * 2 * D);
+    if (!zu || !au) {
+        free(zu);
+        free(au);
+        return ZKO_ENOMEM;
+    }
+    int rc = 0;
+    for (uint64_t i = 0; i < D; ++i) {
+        if (gw[i] <= -lim || gw[i] >= lim) rc = ZKO_ERANGE; /* -G must be in range as well */
+        zu[i] = gw[i];
+        zu[D + i] = -gw[i];
+    }
+    if (!rc) {
+        for (uint64_t i = 0; i < 2 * D; ++i) {
+            const int64_t zp = (zu[i] + half) >> rb; /* zkReLU's rescaling: round half up */
+            au[i] = fe_from_u64(zp > 0 ? (uint64_t)zp : 0);
+        }
+        fe pt0[41], pt1[41];
+        pt0[0] = fe_from_u64(0);
+        pt1[0] = fe_from_u64(1);
+        for (int c = 0; c < ld; ++c) pt0[1 + c] = pt1[1 + c] = p[c];
+        const fe* pts[2] = {pt0, pt1};
+        wbuf wb = {proof, (size_t)cap, 0};
+        wb_u32(&wb, 0x50554B5Au); /* "ZKUP" */
+        wb_u32(&wb, (uint32_t)ld);
+        wb_u32(&wb, (uint32_t)q);
+        wb_u32(&wb, (uint32_t)rb);
+        for (int k = 0; k < 4; ++k) wb_u32(&wb, 0);
+        ms_info ms;
+        rc = stack_merge_core(au, 2, D, 2, pts, ts, 0, &wb, &ms);
+        if (!rc) {
+            fe uz[40];
+            ts_draw(ts, li, uz);
+            fe* four = (fe*)malloc(sizeof(fe) * 4 * (size_t)li);
+            if (!four) rc = ZKO_ENOMEM;
+            if (!rc) {
+                for (int c = 0; c < li; ++c) four[c] = four[2 * li + c] = four[3 * li + c] = uz[c];
+                four[li] = ms.vn[0];
+                for (int c = 0; c < ld; ++c) four[li + 1 + c] = ms.v[c];
+                zk_info zi;
+                rc = zkrelu_core(zu, 0, 2 * D, q, rb, ts, four, 0, &wb, &zi);
+                free(four);
+            }
+        }
+        if (!rc) {
+            *proof_len = wb.len;
+            if (wb.len > wb.cap) rc = ZKO_ESMALL;
+        }
+    }
+    free(zu);
+    free(au);
+    return rc;
+}
+
 int zko_threads(void) { return max_threads(); }

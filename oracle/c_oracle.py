@@ -232,6 +232,13 @@ def zkrelu_prove(z, ga, q, r_bits, ts, points=None, bind_points=True):
                 C.c_int(q), C.c_int(r_bits), pts, C.c_int(1 if bind_points else 0), C.c_void_p(ts._h))
 
 
+def update_prove(gw, q, r_bits, ts):
+    """gw: integer array, a power of two of entries.  Returns the proof bytes (oracle.protocols.update_prove)."""
+    gg = _i64(gw)
+    return _run(load().zko_update_prove, gg.ctypes.data_as(C.c_void_p), C.c_uint64(gg.shape[0]), C.c_int(q),
+                C.c_int(r_bits), C.c_void_p(ts._h))
+
+
 def reindex_prove(x_le, n, d, maps, points, u, ts, bind_statement=True):
     k = len(maps)
     marr = [np.ascontiguousarray(np.asarray(m, dtype=np.int32)) for m in maps]

@@ -186,6 +186,28 @@ def test_stack_merge_matches_python_tier(n, d, k, bind):
     _same(cts, ts, c_oracle.stack_merge_prove(x, n, d, pts, cts, bind_statement=bind), buf)
 
 
+@pytest.mark.parametrize("d,q,r", [(1, 5, 3), (2, 4, 4), (8, 6, 4), (64, 10, 6), (256, 32, 30), (128, 33, 30)])
+def test_update_matches_python_tier(d, q, r):
+    rng = np.random.default_rng(d + q)
+    lim = 1 << (q + r - 1)
+    g = rng.integers(-lim + 1, lim, d, dtype=np.int64)
+    half = 1 << (r - 1)
+    for k, v in enumerate([half, -half, 0, lim - 1, -lim + 1]):
+        if k < d:
+            g[k] = v
+    ts, cts = Transcript(16), c_oracle.Transcript(16)
+    buf, _ = P.update_prove([int(x) for x in g], q, r, ts)
+    _same(cts, ts, c_oracle.update_prove(g, q, r, cts), buf)
+
+
+def test_update_range_error_as_in_python_tier():
+    for g in ([1 << 9, 0], [-(1 << 9), 0]):
+        with pytest.raises(ValueError):
+            P.update_prove(g, 5, 5, Transcript(1))
+        with pytest.raises(c_oracle.OracleError):
+            c_oracle.update_prove(np.array(g, dtype=np.int64), 5, 5, c_oracle.Transcript(1))
+
+
 @pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 16, 2, 1), (1, 16, 2, 1), (2, 4, 2, 4), (8, 8, 4, 1)])
 @pytest.mark.parametrize("linked", [False, True, "ft"])
 def test_aggregate_matches_python_tier(layers, width, batch, steps, linked):

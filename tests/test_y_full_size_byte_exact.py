@@ -92,6 +92,33 @@ def test_config3_ft_byte_exact(lib, ctx, capsys):
     _compare(lib, ctx, wit, CONFIG_SEED + 7, False, capsys, "config 3 ft", ft=True)
 
 
+def test_update_2p18_byte_exact(lib, ctx, capsys):
+    """The proof of the parameter update on 2^18 gradients (zkReLU over 2^19 rows of 62 bits, as many rows as the
+    8 x 1024^2 window has): every proof byte, every drawn challenge, the transcript digest against the C tier."""
+    import torch
+    d, q, r = 1 << 18, 32, 30
+    rng = np.random.default_rng(CONFIG_SEED + 71)
+    g = rng.integers(-(1 << 44), 1 << 44, d, dtype=np.int64)
+    g[:4] = [1 << 29, -(1 << 29), 3 << 29, -(3 << 29)]
+    with capsys.disabled():
+        print("\n    oracle update 2^18: start", flush=True)
+        t0 = time.perf_counter()
+        cts = c_oracle.Transcript(CONFIG_SEED + 71)
+        buf = c_oracle.update_prove(g, q, r, cts)
+        print(f"    oracle update 2^18: {time.perf_counter() - t0:.1f} s", flush=True)
+    tr = lib.Transcript(CONFIG_SEED + 71)
+    got = lib.update_prove(ctx, torch.from_numpy(g).cuda(), tr, q, r)
+    assert got["proof"] == buf
+    drawn, k = [], 0
+    want = cts.challenges
+    for v in got["points"]:
+        if k < len(want) and v == want[k]:
+            drawn.append(v)
+            k += 1
+    assert drawn == want
+    assert tr.digest() == cts.digest()
+
+
 def _budget_or_skip(factor, limit_s, name):
     t3 = _t_config3.get("s")
     if t3 is None:
