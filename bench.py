@@ -291,6 +291,10 @@ def main():
         vf_med, _ = timed(lambda: zk.aggregate_verify(ctx, pf3, zk.Transcript(CONFIG_SEED + 3)), 5)
         out["config"]["verify_ms_batch64_8layer_step"] = 1e3 * vf_med
         assert zk.aggregate_verify(ctx, pf3, zk.Transcript(CONFIG_SEED + 3))["verdict"] == 0
+        pl3 = zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + 3), linked=True)["proof"]
+        vl_med, _ = timed(lambda: zk.aggregate_verify(ctx, pl3, zk.Transcript(CONFIG_SEED + 3)), 5)
+        out["config"]["verify_ms_batch64_8layer_step_linked"] = 1e3 * vl_med
+        assert zk.aggregate_verify(ctx, pl3, zk.Transcript(CONFIG_SEED + 3))["verdict"] == 0
         out["config"]["paper_context"] = ("paper: < 1 s per batch-64 update, 8-layer 10M-parameter net, one "
                                           "Tesla A100, whole protocol including commitments (not comparable)")
         del dw

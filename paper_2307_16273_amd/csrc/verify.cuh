@@ -29,8 +29,10 @@ VF_HD Fr mulx(const Fr& a, const Fr& b) {
 }
 
 constexpr uint32_t SC_MAGIC = 0x43534B5Au, ZKAG_MAGIC = 0x47414B5Au, ZKAF_MAGIC = 0x46414B5Au, ZKRL_MAGIC = 0x4C524B5Au,
-                   FT_MAGIC = 0x46534B5Au;
+                   FT_MAGIC = 0x46534B5Au, ZKAL_MAGIC = 0x4C414B5Au, ZKRI_MAGIC = 0x49524B5Au, ZKMS_MAGIC = 0x534D4B5Au,
+                   ZKUP_MAGIC = 0x50554B5Au;
 constexpr int MAX_CHAL = 1024;
+constexpr int MAX_PT = 48;    // coordinates of a point that the program assembles from pieces
 constexpr int MAX_RD = 4;   // elements one read may take
 
 // the proof: 4-byte aligned on the device, every field at a multiple of four bytes
@@ -108,6 +110,24 @@ VF_NI Fr mle_small_serial(const Fr* tab, int lj, const Fr* wbar) {
     return acc;
 }
 
+// beta~(u, j) for an index j of m bits (coordinate 0 pairs with the most significant bit)
+VF_NI Fr beta_index(const Fr* u, int m, uint64_t j) {
+    Fr acc = fr_one();
+    const Fr one = fr_one();
+    for (int k = 0; k < m; ++k) acc = mulx(acc, ((j >> (m - 1 - k)) & 1) ? u[k] : fr_sub(one, u[k]));
+    return acc;
+}
+
+// sum over the slots j of a stack of 2^ln tensors, L per step, that are not a step's last layer, of
+// beta~(u, j) beta~(v, j + 1): the weight P~(v) of the sub-stack "slot (t, l) <- slot (t, l + 1)" (Eq. sc-reindex)
+VF_NI Fr shift_weight_serial(const Fr* u, const Fr* v, int ln, uint64_t L) {
+    Fr acc = fr_zero();
+    const uint64_t n = (uint64_t)1 << ln;
+    for (uint64_t j = 0; j + 1 < n; ++j)
+        if (j % L != L - 1) acc = fr_add(acc, mulx(beta_index(u, ln, j), beta_index(v, ln, j + 1)));
+    return acc;
+}
+
 // What the program needs from its surroundings: the transcript, the challenges drawn so far, reading field
 // elements of the proof.  Two implementations with the same members:
 //   HostCtx  one thread, the byte-wise transcript of the host side;
@@ -118,7 +138,8 @@ VF_NI Fr mle_small_serial(const Fr* tab, int lj, const Fr* wbar) {
 //   absorb_elems(label, src, n)     n elements as they stand in the proof, one-character label
 //   absorb_draw1(label, src, n, skip1, v)  the same (skip1: without element 1), then a draw of one challenge
 //   draw(n)                         a draw of n challenges; both return the index of the first
-//   lagrange(g, npts, v), beta_point(u, v, m), mle_small(tab, lj, wbar)   the verifier's own arithmetic: serial on
+//   lagrange(g, npts, v), beta_point(u, v, m), mle_small(tab, lj, wbar), shift_weight(u, v, ln, L)
+//                                   the verifier's own arithmetic: serial on
 //                                   the host, one term per lane on the device
 struct CtxBase {
     Fr* chal;       // room for MAX_CHAL challenges (Montgomery form)
@@ -170,6 +191,7 @@ struct HostCtx : CtxBase {
     __host__ Fr lagrange(const Fr* g, int npts, const Fr& v) const { return lagrange_serial(inv2, inv6, g, npts, v); }
     __host__ Fr beta_point(const Fr* u, const Fr* v, int m) const { return beta_point_serial(u, v, m); }
     __host__ Fr mle_small(const Fr* tab, int lj, const Fr* wbar) const { return mle_small_serial(tab, lj, wbar); }
+    __host__ Fr shift_weight(const Fr* u, const Fr* v, int ln, uint64_t L) const { return shift_weight_serial(u, v, ln, L); }
     __host__ int absorb_draw1(char label, const uint8_t* src, int n, bool skip1, Fr* v) {
         uint8_t msg[32 * MAX_RD];
         int nm = 0;
@@ -255,6 +277,21 @@ struct DevCtx : CtxBase {
             acc = mulx(acc, lane0(wave_product(t)));
         }
         return acc;
+    }
+    __device__ Fr shift_weight(const Fr* u, const Fr* v, int ln, uint64_t L) {   // one slot per lane at a time
+        const int lane = threadIdx.x & 63;
+        const uint64_t n = (uint64_t)1 << ln;
+        Fr t = fr_zero();
+        for (uint64_t j0 = 0; j0 < n; j0 += 64) {
+            const uint64_t j = j0 + (uint64_t)lane;
+            if (j + 1 < n && j % L != L - 1) t = fr_add(t, mulx(beta_index(u, ln, j), beta_index(v, ln, j + 1)));
+        }
+        for (int off = 32; off >= 1; off >>= 1) {
+            Fr y;
+            for (int l = 0; l < 8; ++l) y.v[l] = __shfl_down(t.v[l], off, 64);
+            t = fr_add(t, y);
+        }
+        return lane0(t);
     }
     __device__ Fr mle_small(const Fr* tab, int lj, const Fr* wbar) {   // lj <= 6
         const int lane = threadIdx.x & 63;
@@ -411,8 +448,13 @@ VF_HD bool rd_sc_header(Reader& r, ScHeader& h) {
 
 // Eq. exm-matmul-batched, the prover's g_t form: header, draw (w, u0, u1), claim_0, rounds over (n, i), the
 // finals (beta~(w, v_n), X0~, X1~) with beta~(w, v_n) recomputed and their product against the last claim.
+struct MatmulOut {
+    int cw, cv;        // first challenge of (w, u0, u1) and of the rounds (v_n, v_i)
+    Fr claim0, f1, f2; // Y~(w, u0, u1), X0~(v_n, u0, v_i), X1~(v_n, v_i, u1)
+};
+
 template <class C>
-VF_NI int matmul(C& c, Reader& r, uint64_t n, uint64_t d1, uint64_t d2, uint64_t d3) {
+VF_NI int matmul(C& c, Reader& r, uint64_t n, uint64_t d1, uint64_t d2, uint64_t d3, MatmulOut* out = nullptr) {
     const int ln = ilog2(n), l1 = ilog2(d1), l2 = ilog2(d2), l3 = ilog2(d3);
     ScHeader h;
     if (!rd_sc_header(r, h) || h.n_finals != 3 || h.degree != 3 || (int)h.rounds != ln + l2) return 10;
@@ -424,6 +466,7 @@ VF_NI int matmul(C& c, Reader& r, uint64_t n, uint64_t d1, uint64_t d2, uint64_t
     c.rd_elems(r, 1, &claim, &src);
     if (r.bad || c.overflow) return 11;
     c.absorb_elems('c', src, 1);
+    const Fr claim0 = claim;
     int cv;
     const int rc = rounds(c, r, ln + l2, 3, claim, &cv);
     if (rc) return 20 + rc;
@@ -434,6 +477,13 @@ VF_NI int matmul(C& c, Reader& r, uint64_t n, uint64_t d1, uint64_t d2, uint64_t
     c.absorb_elems('f', fsrc, 3);
     if (!fr_eq(f[0], c.beta_point(c.chal + cw, c.chal + cv, ln))) return 13;
     if (!fr_eq(mulx(mulx(f[0], f[1]), f[2]), claim)) return 14;
+    if (out) {
+        out->cw = cw;
+        out->cv = cv;
+        out->claim0 = claim0;
+        out->f1 = f[1];
+        out->f2 = f[2];
+    }
     return 0;
 }
 
@@ -482,12 +532,21 @@ VF_NI int matmul_ft(C& c, Reader& r, uint64_t n, uint64_t d1, uint64_t d2, uint6
     return 0;
 }
 
-// zkReLU with all five points drawn (App. A and the merge of the three claims on aux)
+// zkReLU (App. A and the merge of the three claims on aux).  given == nullptr: all five points drawn (mode 0).
+// Otherwise the four points u_Z, u_A, u_GA, u_GZ (li coordinates each, one after the other) are the caller's,
+// functions of this transcript already (mode 2), and only u_bin is drawn.
+struct ZkOut {
+    Fr c_in[4];
+    int has_ga;
+};
+
 template <class C>
-VF_NI int zkrelu(C& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r_expect) {
+VF_NI int zkrelu(C& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r_expect, const Fr* given = nullptr,
+                 ZkOut* out = nullptr) {
     const uint32_t magic = rd_u32(r), pli = rd_u32(r), q = rd_u32(r), rb = rd_u32(r), has_ga = rd_u32(r), mode = rd_u32(r);
     const uint32_t pad0 = rd_u32(r), pad1 = rd_u32(r);
-    if (r.bad || pad0 != 0 || pad1 != 0 || magic != ZKRL_MAGIC || (int)pli != li_expect || q != q_expect || rb != r_expect || mode != 0 || has_ga > 1)
+    if (r.bad || pad0 != 0 || pad1 != 0 || magic != ZKRL_MAGIC || (int)pli != li_expect || q != q_expect || rb != r_expect ||
+        mode != (given ? 2u : 0u) || has_ga > 1)
         return 1;
     const int li = (int)pli, b = (int)(q + rb);
     if (b < 2 || b > 64 || rb < 1) return 1;
@@ -499,13 +558,34 @@ VF_NI int zkrelu(C& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r_e
     c.rd_elems(r, 4, c_in, &csrc);
     ScHeader h, hm;
     if (!rd_sc_header(r, h) || h.n_finals != 3 || h.degree != 3 || (int)h.rounds != li + lj) return 2;
-    const uint32_t words[4] = {pli, q, rb, has_ga};
-    c.absorb_words("zkrelu", 6, words, 4);
-    const int cu = c.draw(5 * li + lj);   // u_Z, u_A, u_GA, u_GZ (li each), u_bin (li + lj)
+    const Fr *u_z, *u_a, *u_ga, *u_gz;
+    int c_bin;
+    if (given) {
+        const uint32_t words[5] = {pli, q, rb, has_ga, mode};
+        c.absorb_words("zkrelu_at", 9, words, 5);
+        c_bin = c.draw(li + lj);
+        u_z = given;
+        u_a = given + li;
+        u_ga = given + 2 * li;
+        u_gz = given + 3 * li;
+    } else {
+        const uint32_t words[4] = {pli, q, rb, has_ga};
+        c.absorb_words("zkrelu", 6, words, 4);
+        const int cu = c.draw(5 * li + lj);   // u_Z, u_A, u_GA, u_GZ (li each), u_bin (li + lj)
+        u_z = c.chal + cu;
+        u_a = u_z + li;
+        u_ga = u_a + li;
+        u_gz = u_ga + li;
+        c_bin = cu + 4 * li;
+    }
     if (r.bad || c.overflow) return 3;
     c.absorb_elems('c', csrc, 4);
     const int cr = c.draw(2);
     if (c.overflow) return 3;
+    if (out) {
+        for (int k = 0; k < 4; ++k) out->c_in[k] = c_in[k];
+        out->has_ga = (int)has_ga;
+    }
     const Fr rr = c.chal[cr], rp = c.chal[cr + 1], r2 = mulx(rr, rr);
     const Fr w_z = r2, w_a = rr, w_ga = mulx(rp, r2), w_gz = mulx(rp, rr);
     Fr claim;
@@ -540,7 +620,7 @@ VF_NI int zkrelu(C& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r_e
     const Fr* v_i = c.chal + cv;
     const Fr* wbar = c.chal + cv + li;
     const Fr s_w = c.mle_small(s_tab, lj, wbar), sp_w = c.mle_small(sp_tab, lj, wbar);
-    const Fr b_bin = c.beta_point(c.chal + cu + 4 * li, c.chal + cv, li + lj);
+    const Fr b_bin = c.beta_point(c.chal + c_bin, c.chal + cv, li + lj);
     const Fr one = fr_one();
     const Fr ns = fr_sub(one, sg);
     auto side = [&](const Fr& a, const Fr& w_in, const Fr& w_out, const Fr* u_in, const Fr* u_out) {
@@ -548,9 +628,9 @@ VF_NI int zkrelu(C& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r_e
         t = fr_add(t, mulx(mulx(mulx(mulx(w_out, c.beta_point(u_out, v_i, li)), ns), a), sp_w));
         return fr_add(t, mulx(b_bin, fr_sub(mulx(a, a), a)));
     };
-    const Fr fwd = side(a0, w_z, w_a, c.chal + cu, c.chal + cu + li);
-    Fr bwd = mulx(mulx(mulx(w_ga, c.beta_point(c.chal + cu + 2 * li, v_i, li)), a1), s_w);
-    bwd = fr_add(bwd, mulx(mulx(mulx(mulx(w_gz, c.beta_point(c.chal + cu + 3 * li, v_i, li)), ns), a1), sp_w));
+    const Fr fwd = side(a0, w_z, w_a, u_z, u_a);
+    Fr bwd = mulx(mulx(mulx(w_ga, c.beta_point(u_ga, v_i, li)), a1), s_w);
+    bwd = fr_add(bwd, mulx(mulx(mulx(mulx(w_gz, c.beta_point(u_gz, v_i, li)), ns), a1), sp_w));
     bwd = fr_add(bwd, mulx(mulx(rp, b_bin), fr_sub(mulx(a1, a1), a1)));
     if (!fr_eq(fr_add(fwd, bwd), claim)) return 6;   // App. A: the six equations at the challenge point
     // merge of the three claims on aux (degree 2 over 1 + lj variables)
@@ -588,7 +668,244 @@ VF_NI int zkrelu(C& c, Reader& r, int li_expect, uint32_t q_expect, uint32_t r_e
     return 0;
 }
 
-// The whole window ("ZKAG": g_t form; "ZKAF": f_t form for the matrix products).  The context's transcript is
+// One product sumcheck on two tables inside a re-indexing or a merge: header (2 finals, degree 2), claim_0
+// against `expect` and absorbed, the rounds, the two finals absorbed, their product against the last claim.
+template <class C>
+VF_NI int product2(C& c, Reader& r, int nrounds, const Fr& expect, int* cv, Fr* f0, Fr* f1) {
+    ScHeader h;
+    if (!rd_sc_header(r, h) || h.n_finals != 2 || h.degree != 2 || (int)h.rounds != nrounds) return 1;
+    const uint8_t* src = nullptr;
+    Fr claim;
+    c.rd_elems(r, 1, &claim, &src);
+    if (r.bad || !fr_eq(claim, expect)) return 2;
+    c.absorb_elems('c', src, 1);
+    const int rc = rounds(c, r, nrounds, 2, claim, cv);
+    if (rc) return 10 + rc;
+    const uint8_t* fsrc = nullptr;
+    Fr f[2];
+    c.rd_elems(r, 2, f, &fsrc);
+    if (r.bad) return 3;
+    c.absorb_elems('f', fsrc, 2);
+    if (!fr_eq(mulx(f[0], f[1]), claim)) return 4;
+    *f0 = f[0];
+    *f1 = f[1];
+    return 0;
+}
+
+// K <= 2 claims on a stack [n, d] merged into one (Eq. sc-reindex; the "ZKMS" block inside a larger proof):
+// pts[k] = the ln + ld coordinates of claim k, stack coordinates first.  On return claims[k] are the claims the
+// block states, *cvn / *cv the first challenges of the point (v_n, v) of the one claim *left.
+template <class C>
+VF_NI int stack_merge(C& c, Reader& r, uint64_t n, uint64_t d, int K, const Fr* const* pts, Fr* claims, int* cvn, int* cv,
+                      Fr* left) {
+    const int ln = ilog2(n), ld = ilog2(d);
+    int lk = 0;
+    while ((1 << lk) < K) ++lk;
+    const uint32_t magic = rd_u32(r), pn = rd_u32(r), pd = rd_u32(r), pk = rd_u32(r);
+    if (r.bad || magic != ZKMS_MAGIC || pn != (uint32_t)n || pd != (uint32_t)d || (int)pk != K || K < 1 || K > 2) return 1;
+    const uint32_t words[3] = {(uint32_t)n, (uint32_t)d, (uint32_t)K};
+    c.absorb_words("merge_stack", 11, words, 3);
+    const uint8_t* src = nullptr;
+    c.rd_elems(r, K, claims, &src);
+    if (r.bad) return 2;
+    c.absorb_elems('c', src, K);
+    const int cr = c.draw(K);
+    if (c.overflow) return 3;
+    Fr expect = fr_zero();
+    for (int k = 0; k < K; ++k) expect = fr_add(expect, mulx(c.chal[cr + k], claims[k]));
+    int c1;
+    Fr ef, tf;
+    int rc = product2(c, r, lk + ld, expect, &c1, &ef, &tf);
+    if (rc) return 20 + rc;
+    const Fr* rho = c.chal + c1;
+    const Fr* v = c.chal + c1 + lk;
+    Fr e_pub = fr_zero();
+    for (int k = 0; k < K; ++k)
+        e_pub = fr_add(e_pub, mulx(mulx(beta_index(rho, lk, (uint64_t)k), c.chal[cr + k]), c.beta_point(pts[k] + ln, v, ld)));
+    if (!fr_eq(ef, e_pub)) return 4;
+    int c2;
+    Fr pf, xf;
+    rc = product2(c, r, ln, tf, &c2, &pf, &xf);
+    if (rc) return 40 + rc;
+    Fr p_pub = fr_zero();
+    for (int k = 0; k < K; ++k) p_pub = fr_add(p_pub, mulx(beta_index(rho, lk, (uint64_t)k), c.beta_point(pts[k], c.chal + c2, ln)));
+    if (!fr_eq(pf, p_pub)) return 5;
+    *cvn = c2;
+    *cv = c1 + lk;
+    *left = xf;
+    return 0;
+}
+
+// Re-indexing of a stack of n = 2^ln tensors with L per step (Eq. sc-reindex; the "ZKRI" block inside a larger
+// proof): K <= 2 sub-stacks, each the stack itself (shifted[k] == false) or the stack with slot (t, l) <- slot
+// (t, l + 1) and a zero tensor for a step's last layer (shifted[k] == true), with its stack point stack_pts[k].
+template <class C>
+VF_NI int reindex_layers(C& c, Reader& r, uint64_t n, uint64_t L, uint64_t d, int K, const bool* shifted,
+                         const Fr* const* stack_pts, Fr* claims, int* cv, Fr* left) {
+    const int ln = ilog2(n);
+    const uint32_t magic = rd_u32(r), pn = rd_u32(r), pd = rd_u32(r), pk = rd_u32(r);
+    if (r.bad || magic != ZKRI_MAGIC || pn != (uint32_t)n || pd != (uint32_t)d || (int)pk != K || K < 1 || K > 2) return 1;
+    const uint32_t words[3] = {(uint32_t)n, (uint32_t)d, (uint32_t)K};
+    c.absorb_words("reindex", 7, words, 3);
+    const uint8_t* src = nullptr;
+    c.rd_elems(r, K, claims, &src);
+    if (r.bad) return 2;
+    c.absorb_elems('c', src, K);
+    const int cr = c.draw(K);
+    if (c.overflow) return 3;
+    Fr expect = fr_zero();
+    for (int k = 0; k < K; ++k) expect = fr_add(expect, mulx(c.chal[cr + k], claims[k]));
+    Fr pw, xw;
+    const int rc = product2(c, r, ln, expect, cv, &pw, &xw);
+    if (rc) return 20 + rc;
+    Fr p_pub = fr_zero();
+    for (int k = 0; k < K; ++k) {
+        const Fr wk = shifted[k] ? c.shift_weight(stack_pts[k], c.chal + *cv, ln, L) : c.beta_point(stack_pts[k], c.chal + *cv, ln);
+        p_pub = fr_add(p_pub, mulx(c.chal[cr + k], wk));
+    }
+    if (!fr_eq(pw, p_pub)) return 4;
+    *left = xw;
+    return 0;
+}
+
+VF_HD void put_coords(Fr* dst, int* at, const Fr* src, int n) {
+    for (int i = 0; i < n; ++i) dst[(*at)++] = src[i];
+}
+
+// The window with its claims chained ("ZKAL"): the three matrix products, zkReLU at the points they leave, the
+// re-indexing of A, G_Z and W, the merges on A and W; every link between the parts is checked here (Sec. 3.2;
+// Protocol zkdl: one claim per stack is left).  Stages in the codes: 2..4 the matrix products, 5 / 6 zkReLU,
+// 7 the links, 8..10 the re-indexings, 11 / 12 the merges.
+template <class C>
+VF_NI int aggregate_linked(C& c, Reader& r, uint32_t L, uint32_t B, uint32_t width, uint32_t T, uint32_t Q, uint32_t R) {
+    const uint32_t words[6] = {L, B, width, T, Q, R};
+    c.absorb_words("aggregate_linked", 16, words, 6);
+    const uint64_t n = (uint64_t)L * T;
+    const int ln = ilog2(n), lb = ilog2(B), lw = ilog2(width), ll = ilog2(L), lt = ln - ll;
+    if (ln + lb + lw + lw > MAX_PT) return 101;
+    const uint64_t dims[3][3] = {{B, width, width}, {B, width, width}, {width, B, width}};
+    MatmulOut m[3];
+    for (int fam = 0; fam < 3; ++fam) {
+        const int rc = matmul(c, r, n, dims[fam][0], dims[fam][1], dims[fam][2], &m[fam]);
+        if (rc) return 100 * (2 + fam) + rc;
+    }
+    const MatmulOut &f = m[0], &g = m[1], &h = m[2];
+    // challenge layout of a matrix product: w (ln), u0 (l1), u1 (l3) from cw; v_n (ln), v_i (l2) from cv
+    const Fr *f_w = c.chal + f.cw, *f_u0 = f_w + ln, *f_u1 = f_u0 + lb, *f_vn = c.chal + f.cv, *f_vi = f_vn + ln;
+    const Fr *g_w = c.chal + g.cw, *g_u0 = g_w + ln, *g_u1 = g_u0 + lb, *g_vn = c.chal + g.cv, *g_vi = g_vn + ln;
+    const Fr *h_w = c.chal + h.cw, *h_u0 = h_w + ln, *h_u1 = h_u0 + lw, *h_vn = c.chal + h.cv, *h_vi = h_vn + ln;
+    (void)h_w;
+    const int li = ln + lb + lw;
+    Fr given[4 * MAX_PT];
+    int at = 0;
+    put_coords(given, &at, f_w, li);                                                              // u_Z
+    put_coords(given, &at, f_vn, ln), put_coords(given, &at, f_u0, lb), put_coords(given, &at, f_vi, lw);   // u_A
+    put_coords(given, &at, g_w, li);                                                              // u_GA
+    put_coords(given, &at, h_vn, ln), put_coords(given, &at, h_vi, lb), put_coords(given, &at, h_u1, lw);   // u_GZ
+    ZkOut zk;
+    int rc = zkrelu(c, r, li, Q, R, given, &zk);
+    if (rc) return (rc >= 100 ? 600 + rc - 100 : 500 + rc);
+    if (!fr_eq(zk.c_in[2], g.claim0)) return 701;   // G_A is the gradA family's product
+    // the last layer's share of forward's claim_0 and of gradW's final on G_Z: where its weight beta~(layer
+    // coordinates, L - 1) vanishes there is no share to take
+    {
+        Fr fac_f = fr_one(), fac_h = fr_one();
+        for (int k = lt; k < ln; ++k) {
+            fac_f = mulx(fac_f, f_w[k]);
+            fac_h = mulx(fac_h, h_vn[k]);
+        }
+        const Fr zero = fr_zero();
+        if (fr_eq(fac_f, zero) && !fr_eq(f.claim0, zk.c_in[0])) return 702;
+        if (fr_eq(fac_h, zero) && !fr_eq(h.f2, zk.c_in[3])) return 703;
+    }
+    // A: itself and its shifted stack at forward's stack point
+    Fr cl[2], a_left, gz_left, w_left;
+    int c_ra, c_rg, c_rw;
+    {
+        const bool sh[2] = {false, true};
+        const Fr* sp[2] = {f_vn, f_vn};
+        rc = reindex_layers(c, r, n, L, (uint64_t)B * width, 2, sh, sp, cl, &c_ra, &a_left);
+        if (rc) return 800 + rc;
+        if (!fr_eq(cl[0], f.f1) || !fr_eq(cl[1], zk.c_in[1])) return 704;   // the next layer's input is this ReLU's output
+    }
+    {
+        const bool sh[1] = {true};
+        const Fr* sp[1] = {g_vn};
+        rc = reindex_layers(c, r, n, L, (uint64_t)B * width, 1, sh, sp, cl, &c_rg, &gz_left);
+        if (rc) return 900 + rc;
+        if (!fr_eq(cl[0], g.f1)) return 705;
+        rc = reindex_layers(c, r, n, L, (uint64_t)width * width, 1, sh, sp, cl, &c_rw, &w_left);
+        if (rc) return 1000 + rc;
+        if (!fr_eq(cl[0], g.f2)) return 706;
+    }
+    (void)gz_left;
+    (void)c_rg;
+    // the two claims on A and the two on W become one each
+    Fr p0[MAX_PT], p1[MAX_PT], one_left;
+    int cvn, cv;
+    {
+        at = 0;
+        put_coords(p0, &at, c.chal + c_ra, ln), put_coords(p0, &at, f_u0, lb), put_coords(p0, &at, f_vi, lw);
+        at = 0;
+        put_coords(p1, &at, h_vn, ln), put_coords(p1, &at, h_vi, lb), put_coords(p1, &at, h_u0, lw);
+        const Fr* pts[2] = {p0, p1};
+        rc = stack_merge(c, r, n, (uint64_t)B * width, 2, pts, cl, &cvn, &cv, &one_left);
+        if (rc) return 1100 + rc;
+        if (!fr_eq(cl[0], a_left) || !fr_eq(cl[1], h.f1)) return 707;
+    }
+    {
+        at = 0;
+        put_coords(p0, &at, f_vn, ln), put_coords(p0, &at, f_vi, lw), put_coords(p0, &at, f_u1, lw);
+        at = 0;
+        put_coords(p1, &at, c.chal + c_rw, ln), put_coords(p1, &at, g_u1, lw), put_coords(p1, &at, g_vi, lw);
+        const Fr* pts[2] = {p0, p1};
+        rc = stack_merge(c, r, n, (uint64_t)width * width, 2, pts, cl, &cvn, &cv, &one_left);
+        if (rc) return 1200 + rc;
+        if (!fr_eq(cl[0], f.f2) || !fr_eq(cl[1], w_left)) return 708;
+    }
+    return 0;
+}
+
+// The proof of the parameter update ("ZKUP"; Sec. 5, Example FCNN, last item): the two claims Au~(0, p), Au~(1, p)
+// merged on the stack [2, D], then zkReLU's forward half on [G_W; -G_W] at u_A = the merged point and a drawn u_Z.
+// Stages in the codes: 13 header, 14 the merge, 15 / 16 zkReLU, 17 the links.
+template <class C>
+VF_NI int update(C& c, Reader& r, uint32_t ld, uint32_t Q, uint32_t R) {
+    if (ld > 30 || Q + R > 63) return 1301;
+    const uint32_t words[3] = {ld, Q, R};
+    c.absorb_words("update", 6, words, 3);
+    const int cp = c.draw((int)ld);
+    if (c.overflow) return 1302;
+    Fr p0[MAX_PT], p1[MAX_PT];
+    p0[0] = fr_zero();
+    p1[0] = fr_one();
+    for (uint32_t k = 0; k < ld; ++k) p0[1 + k] = p1[1 + k] = c.chal[cp + (int)k];
+    const Fr* pts[2] = {p0, p1};
+    Fr cl[2], left;
+    int cvn, cv;
+    int rc = stack_merge(c, r, 2, (uint64_t)1 << ld, 2, pts, cl, &cvn, &cv, &left);
+    if (rc) return 1400 + rc;
+    const int li = (int)ld + 1;
+    const int cz = c.draw(li);
+    if (c.overflow) return 1302;
+    Fr given[4 * MAX_PT];
+    int at = 0;
+    put_coords(given, &at, c.chal + cz, li);
+    put_coords(given, &at, c.chal + cvn, 1), put_coords(given, &at, c.chal + cv, (int)ld);
+    put_coords(given, &at, c.chal + cz, li);
+    put_coords(given, &at, c.chal + cz, li);
+    ZkOut zk;
+    rc = zkrelu(c, r, li, Q, R, given, &zk);
+    if (rc) return (rc >= 100 ? 1600 + rc - 100 : 1500 + rc);
+    if (zk.has_ga != 0) return 1701;
+    if (!fr_eq(zk.c_in[1], left)) return 1702;   // zkReLU starts from the merged claim on Au
+    const Fr zero = fr_zero();
+    if (!fr_eq(zk.c_in[2], zero) || !fr_eq(zk.c_in[3], zero)) return 1703;
+    return 0;
+}
+
+// A whole proof: a window ("ZKAG": g_t form; "ZKAF": f_t form for the matrix products; "ZKAL": the claims chained)
+// or a parameter update ("ZKUP").  The context's transcript is
 // the one before the proof and, on return, after it; c.chal / c.n_chal every challenge in draw order; c.inv2 and
 // c.inv6 are 1/2 and 1/6 (checked here).
 template <class C>
@@ -603,8 +920,20 @@ VF_HD int aggregate(C& c, const uint8_t* proof, size_t len) {
     }
     const uint32_t magic = rd_u32(r), L = rd_u32(r), B = rd_u32(r), width = rd_u32(r), T = rd_u32(r), Q = rd_u32(r), R = rd_u32(r);
     const uint32_t pad = rd_u32(r);
-    if (r.bad || pad != 0 || (magic != ZKAG_MAGIC && magic != ZKAF_MAGIC)) return 100;
+    if (r.bad) return 100;
+    if (magic == ZKUP_MAGIC) {   // "ZKUP", log2 D, Q, R, 0, 0, 0, 0
+        if (T != 0 || Q != 0 || R != 0 || pad != 0) return 100;
+        const int rc = update(c, r, L, B, width);
+        if (rc) return rc;
+        return r.at == len ? 0 : 103;
+    }
+    if (pad != 0 || (magic != ZKAG_MAGIC && magic != ZKAF_MAGIC && magic != ZKAL_MAGIC)) return 100;
     if (ilog2(L) < 0 || ilog2(B) < 0 || ilog2(width) < 0 || ilog2(T) < 0) return 101;
+    if (magic == ZKAL_MAGIC) {
+        const int rc = aggregate_linked(c, r, L, B, width, T, Q, R);
+        if (rc) return rc;
+        return r.at == len ? 0 : 103;
+    }
     const bool ft = magic == ZKAF_MAGIC;
     const uint32_t words[6] = {L, B, width, T, Q, R};
     if (ft) c.absorb_words("aggregate_ft", 12, words, 6);

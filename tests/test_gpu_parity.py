@@ -967,6 +967,59 @@ def test_gpu_verifier_agrees_with_the_oracles(lib, ctx, layers, width, batch, st
     assert lib.aggregate_verify(ctx, proof, lib.Transcript(37))["verdict"] != 0     # another transcript
 
 
+@pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 32, 8, 1), (1, 16, 2, 1), (8, 16, 4, 16)])
+def test_gpu_verifier_on_linked_windows(lib, ctx, layers, width, batch, steps):
+    """aggregate_verify on a chained window: the library's own proof accepted with the oracle's challenges and
+    transcript state; tampered proofs refused with the verdict the same program gives on the CPU."""
+    say(f"aggregate_verify (linked) L={layers} w={width} B={batch} T={steps}")
+    wit = fcnn_window(CONFIG_SEED + 85 + layers, layers, width, batch, steps)
+    tr = lib.Transcript(38)
+    got = lib.aggregate_prove(ctx, to_cuda_witness(wit), tr, linked=True)
+    ots = OracleTranscript(38)
+    P.aggregate_linked_verify(got["proof"], ots)
+    tv = lib.Transcript(38)
+    ver = lib.aggregate_verify(ctx, got["proof"], tv)
+    assert ver["verdict"] == 0, ver["verdict"]
+    assert ver["points"] == ots.challenges
+    assert tv.digest() == ots.digest() == tr.digest()
+    proof = got["proof"]
+    n = len(proof)
+    for pos in (5, 40, 100, n // 5, n // 3, n // 2, (2 * n) // 3, (3 * n) // 4, (5 * n) // 6, n - 400, n - 200, n - 1):
+        bad = bytearray(proof)
+        bad[pos] ^= 0x10
+        t1, t2 = lib.Transcript(38), lib.Transcript(38)
+        before = t1.digest()
+        on_gpu = lib.aggregate_verify(ctx, bytes(bad), t1)
+        on_cpu = lib.aggregate_verify(None, bytes(bad), t2)
+        assert on_gpu["verdict"] != 0 and on_gpu["verdict"] == on_cpu["verdict"], pos
+        assert t1.digest() == before
+    assert lib.aggregate_verify(ctx, proof, lib.Transcript(39))["verdict"] != 0
+
+
+@pytest.mark.parametrize("d,q,r", [(1, 5, 3), (64, 10, 6), (4096, 32, 30)])
+def test_gpu_verifier_on_update_proofs(lib, ctx, d, q, r):
+    say(f"aggregate_verify (update) D={d}")
+    g = _update_gradients(d + 3, d, q, r)
+    tr = lib.Transcript(41)
+    got = lib.update_prove(ctx, g, tr, q, r)
+    ots = OracleTranscript(41)
+    P.update_verify(got["proof"], d.bit_length() - 1, q, r, ots)
+    tv = lib.Transcript(41)
+    ver = lib.aggregate_verify(ctx, got["proof"], tv)
+    assert ver["verdict"] == 0, ver["verdict"]
+    assert ver["points"] == ots.challenges
+    assert tv.digest() == ots.digest() == tr.digest()
+    proof = got["proof"]
+    n = len(proof)
+    for pos in (5, 13, 40, 100, n // 4, n // 2, n - 300, n - 1):
+        bad = bytearray(proof)
+        bad[pos] ^= 0x10
+        t1, t2 = lib.Transcript(41), lib.Transcript(41)
+        on_gpu = lib.aggregate_verify(ctx, bytes(bad), t1)
+        on_cpu = lib.aggregate_verify(None, bytes(bad), t2)
+        assert on_gpu["verdict"] != 0 and on_gpu["verdict"] == on_cpu["verdict"], pos
+
+
 @pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 32, 8, 1), (1, 16, 2, 1), (2, 4, 2, 4),
                                                       (4, 16, 8, 4)])
 def test_aggregate_linked(lib, ctx, layers, width, batch, steps):
@@ -1181,6 +1234,9 @@ def test_config3_aggregate_linked_by_properties(lib, ctx):
     ots = OracleTranscript(CONFIG_SEED + 4)
     left = P.aggregate_linked_verify(got["proof"], ots)
     assert tr.digest() == ots.digest()
+    tv = lib.Transcript(CONFIG_SEED + 4)
+    ver = lib.aggregate_verify(ctx, got["proof"], tv)                 # the library's own verifier, on the GPU
+    assert ver["verdict"] == 0 and ver["points"] == ots.challenges and tv.digest() == ots.digest()
     ln, lb = 3, 6
     for name in ("A", "GZ", "W"):
         rows_bits = lb if name != "W" else 10
@@ -1222,6 +1278,9 @@ def test_large_aggregates_by_properties(lib, ctx, name, layers, width, batch, st
     left = P.aggregate_linked_verify(got["proof"], ots)
     assert tr.digest() == ots.digest()
     assert got["claims_left"] == expected_claims_linked(left)
+    tv = lib.Transcript(CONFIG_SEED + cfg + 1)
+    ver = lib.aggregate_verify(ctx, got["proof"], tv)
+    assert ver["verdict"] == 0 and ver["points"] == ots.challenges and tv.digest() == ots.digest()
     ln, lb, lw = (layers * steps).bit_length() - 1, batch.bit_length() - 1, width.bit_length() - 1
     for nm in ("A", "GZ", "W"):
         rows_bits = lb if nm != "W" else lw

@@ -110,3 +110,50 @@ def test_host_verifier_accepts_the_oracles_proofs_and_rejects_tampering():
             # truncated and extended proofs
             assert zk.aggregate_verify(None, buf[:-1], _host_transcript(9))["verdict"] != 0
             assert zk.aggregate_verify(None, buf + b"\x00", _host_transcript(9))["verdict"] != 0
+
+
+def _flip_everything(buf, seed, step=1):
+    for pos in range(0, len(buf), step):
+        bad = bytearray(buf)
+        bad[pos] ^= 0x04
+        tr2 = _host_transcript(seed)
+        before = tr2.digest()
+        assert zk.aggregate_verify(None, bytes(bad), tr2)["verdict"] != 0, pos
+        assert tr2.digest() == before
+    assert zk.aggregate_verify(None, buf, _host_transcript(seed + 1))["verdict"] != 0
+    assert zk.aggregate_verify(None, buf[:-1], _host_transcript(seed))["verdict"] != 0
+    assert zk.aggregate_verify(None, buf + b"\x00", _host_transcript(seed))["verdict"] != 0
+
+
+def test_host_verifier_on_linked_windows():
+    """The chained window ("ZKAL"): accepted with the oracle's challenges and transcript state; every link is
+    checked (a flip of any byte is refused, also where only a link between two parts notices it)."""
+    from oracle import protocols as P
+    from workloads import fcnn_window, CONFIG_SEED
+    for shape in ((2, 8, 4, 2), (1, 4, 2, 1), (4, 4, 2, 2)):
+        wit = fcnn_window(CONFIG_SEED + 131, *shape)
+        ots = OracleTranscript(11)
+        buf, _ = P.aggregate_linked_prove(wit, ots)
+        tr = _host_transcript(11)
+        got = zk.aggregate_verify(None, buf, tr)
+        assert got["verdict"] == 0, got["verdict"]
+        assert got["points"] == ots.challenges
+        assert tr.digest() == ots.digest()
+        _flip_everything(buf, 11, step=1 if shape[0] == 1 else 3)
+
+
+def test_host_verifier_on_update_proofs():
+    from oracle import protocols as P
+    import numpy as np
+    for d, q, r in ((1, 5, 3), (8, 6, 4), (32, 32, 30)):
+        rng = np.random.default_rng(d)
+        lim = 1 << (q + r - 1)
+        g = [int(x) for x in rng.integers(-lim + 1, lim, d)]
+        ots = OracleTranscript(12)
+        buf, _ = P.update_prove(g, q, r, ots)
+        tr = _host_transcript(12)
+        got = zk.aggregate_verify(None, buf, tr)
+        assert got["verdict"] == 0, got["verdict"]
+        assert got["points"] == ots.challenges
+        assert tr.digest() == ots.digest()
+        _flip_everything(buf, 12)
