@@ -544,6 +544,46 @@ def test_too_small_buffers_leave_the_transcript_untouched(lib, ctx):
     assert tr2.digest() == ots.digest()
 
 
+def test_too_small_buffers_in_the_widened_calls(lib, ctx):
+    """update_prove and sumcheck_matmul_general: the size query and a short claims list change nothing."""
+    import ctypes as C
+    say("ZKDL_ESMALL in update_prove and sumcheck_matmul_general")
+    g = _update_gradients(5, 8, 6, 4)
+    raw = lib.load_library().update_prove
+    tr = lib.Transcript(3)
+    before = tr.digest()
+    need, npts = C.c_size_t(0), C.c_size_t(0)
+    rc = raw(ctx.handle, g.ctypes.data, 8, 6, 4, 0, tr.handle, None, C.byref(need), None, C.byref(npts), None, None)
+    assert rc == -5 and tr.digest() == before
+    ots = OracleTranscript(3)
+    buf, _ = P.update_prove([int(x) for x in g], 6, 4, ots)
+    assert need.value == len(buf) and npts.value == len(ots.challenges) + 3 * 4     # three copied points of 1 + 3 coordinates
+    claims = (lib.binding.Claim * 2)() if hasattr(lib, "binding") else None
+    if claims is not None:
+        ncl = C.c_size_t(2)
+        pts = C.create_string_buffer(32 * 1024)
+        npts = C.c_size_t(1024)
+        rc = raw(ctx.handle, g.ctypes.data, 8, 6, 4, 0, tr.handle, None, None, pts, C.byref(npts), claims, C.byref(ncl))
+        assert rc == -5 and ncl.value == 3 and tr.digest() == before
+    got = lib.update_prove(ctx, g, tr, 6, 4)
+    assert got["proof"] == buf and tr.digest() == ots.digest()
+    # the general aggregated form
+    x0 = np.arange(16, dtype=np.int64).reshape(2, 2, 4) - 5
+    x1 = np.arange(16, dtype=np.int64).reshape(2, 4, 2) - 7
+    y = np.einsum("nij,njk->nik", x0, x1)
+    a, b, c = [lib.fr_tensor_upload(ctx, t, t.shape) for t in (x0, x1, y)]
+    tr = lib.Transcript(4)
+    before = tr.digest()
+    need = C.c_size_t(0)
+    rc = lib.load_library().sumcheck_matmul_general(ctx.handle, a.handle, b.handle, c.handle, tr.handle, None, C.byref(need),
+                                                    None, None, None)
+    ots = OracleTranscript(4)
+    buf, _ = P.matmul_general_prove(fr_array(x0), [2, 2, 4], fr_array(x1), [2, 4, 2], fr_array(y), ots)
+    assert rc == -5 and need.value == len(buf) and tr.digest() == before
+    got = lib.sumcheck_matmul_general(ctx, a, b, c, tr)
+    assert got["proof"] == buf and tr.digest() == ots.digest()
+
+
 def test_chained_calls_share_one_transcript(lib, ctx):
     say("chained calls")
     n = 64
