@@ -268,7 +268,9 @@ def main():
         # the parameter update of the step: rounding of the 8 x 1024^2 gradient stack proved by zkReLU
         gw = torch.from_numpy(np.random.default_rng(CONFIG_SEED + 33).integers(-(1 << 44), 1 << 44, 1 << 23,
                                                                                   dtype=np.int64)).cuda()
-        up_med, _ = timed(lambda: zk.update_prove(ctx, gw, zk.Transcript(CONFIG_SEED + 33), 32, 30), 3)
+        # (Q, R) = (26, 30): learning rate 2^-14 on 16 fractional bits, gradients below 2^55; 56 bits is the widest
+        # recomposition whose first two rounds run on the integers
+        up_med, _ = timed(lambda: zk.update_prove(ctx, gw, zk.Transcript(CONFIG_SEED + 33), 26, 30), 3)
         out["config"]["update_proof_ms_GW_stack_2p23"] = 1e3 * up_med
         del gw
         # commitments to the window's int32 stacks (Protocol zkdl, the commit line): rows of sqrt(size) entries
