@@ -450,7 +450,7 @@ int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_trans
 /* ---- verifier (Sec. 2.2: the round checks; App. A: the final claim of zkReLU; App. B: the verifier's side of
  * both aggregated protocols; Sec. 6: verification is sequential) ----
  * aggregate_verify replays, on the GPU (one block, the transcript steps shared out among its lanes), a proof of
- * aggregate_prove ("ZKAG"), aggregate_prove_ft ("ZKAF"), aggregate_prove_linked ("ZKAL") or update_prove ("ZKUP")
+ * aggregate_prove ("ZKAG"), aggregate_prove_ft ("ZKAF"), aggregate_prove_linked ("ZKAL"), update_prove ("ZKUP") or sumcheck_matmul_general ("ZKGA")
  * on the transcript `tr` as it stood before that call: it re-derives every challenge, checks every round
  * (g_t(0) + g_t(1) = claim, or (1 - w_t) f_t(0) + w_t f_t(1) = claim), every final claim (the recomputed
  * equality-polynomial values, the six zkReLU equations at the challenge point, the merge of the claims on aux,
@@ -462,7 +462,8 @@ int aggregate_prove_linked(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_trans
  * carries) and claims_out / nclaims the claims left to open (as aggregate_prove reports them; none for the other
  * forms, whose claims the caller reads from the prover's list).  *verdict != 0: rejected, 100 x stage + detail
  * (stage 1 header, 2 forward, 3 gradA, 4 gradW, 5 zkReLU, 6 its merge, 7 a link of a chained window, 8 - 10 the
- * re-indexings of A, G_Z, W, 11 - 12 the merges on A and W, 13 - 17 the parts of an update proof); the transcript
+ * re-indexings of A, G_Z, W, 11 - 12 the merges on A and W, 13 - 17 the parts of an update proof, 18 the general
+ * aggregated form); the transcript
  * is untouched.  The return value is ZKDL_OK whenever the verification ran.  zkdl_host_aggregate_verify: the same
  * program compiled for the CPU. */
 int aggregate_verify(zkdl_ctx* ctx, const uint8_t* proof, size_t proof_len, zkdl_transcript* tr, int* verdict,

@@ -30,7 +30,7 @@ VF_HD Fr mulx(const Fr& a, const Fr& b) {
 
 constexpr uint32_t SC_MAGIC = 0x43534B5Au, ZKAG_MAGIC = 0x47414B5Au, ZKAF_MAGIC = 0x46414B5Au, ZKRL_MAGIC = 0x4C524B5Au,
                    FT_MAGIC = 0x46534B5Au, ZKAL_MAGIC = 0x4C414B5Au, ZKRI_MAGIC = 0x49524B5Au, ZKMS_MAGIC = 0x534D4B5Au,
-                   ZKUP_MAGIC = 0x50554B5Au;
+                   ZKUP_MAGIC = 0x50554B5Au, ZKGA_MAGIC = 0x41474B5Au;
 constexpr int MAX_CHAL = 1024;
 constexpr int MAX_PT = 48;    // coordinates of a point that the program assembles from pieces
 constexpr int MAX_RD = 4;   // elements one read may take
@@ -904,8 +904,52 @@ VF_NI int update(C& c, Reader& r, uint32_t ld, uint32_t Q, uint32_t R) {
     return 0;
 }
 
+// The batched matrix product in the general aggregated form ("ZKGA"; Eq. tensor-op-aggr, Protocol tensor-op-aggr):
+// stack rounds with f_t starting from the claim 0, the sumcheck over (i0, i1, j), and the final check
+// beta~(u, v_i) (D2^-1 Y~ - X0~ X1~) = last claim.  Stage 18 in the codes.
+template <class C>
+VF_NI int matmul_general(C& c, Reader& r, uint32_t ln, uint32_t l1, uint32_t l3, uint32_t l2) {
+    if (ln > 13 || l1 > 16 || l2 > 16 || l3 > 16) return 1801;
+    const uint32_t words[4] = {1u << ln, 1u << l1, 1u << l2, 1u << l3};
+    c.absorb_words("tensor_op_aggr", 14, words, 4);
+    const int cw = c.draw((int)(ln + l1 + l3));
+    if (c.overflow) return 1802;
+    const Fr one = fr_one();
+    Fr claim = fr_zero();
+    for (uint32_t t = 0; t < ln; ++t) {
+        Fr f[3];
+        const uint8_t* fs = nullptr;
+        c.rd_elems(r, 3, f, &fs);
+        if (r.bad) return 1803;
+        const Fr wt = c.chal[cw + (int)t];
+        if (!fr_eq(fr_add(mulx(fr_sub(one, wt), f[0]), mulx(wt, f[1])), claim)) return 1804;
+        Fr v;
+        c.absorb_draw1('f', fs, 3, false, &v);
+        if (c.overflow) return 1802;
+        claim = c.lagrange(f, 3, v);
+    }
+    ScHeader h;
+    if (!rd_sc_header(r, h) || h.n_finals != 3 || h.degree != 2 || h.rounds != l1 + l3 + l2) return 1805;
+    Fr inner0;
+    c.rd_elems(r, 1, &inner0, nullptr);
+    if (r.bad || !fr_eq(inner0, claim)) return 1806;   // written, not absorbed: the transcript fixes it
+    int cv;
+    const int rc = rounds(c, r, (int)(l1 + l3 + l2), 2, claim, &cv);
+    if (rc) return 1810 + rc;
+    const uint8_t* fsrc = nullptr;
+    Fr f[3];
+    c.rd_elems(r, 3, f, &fsrc);
+    if (r.bad) return 1807;
+    c.absorb_elems('f', fsrc, 3);
+    Fr dinv = one;
+    for (uint32_t k = 0; k < l2; ++k) dinv = mulx(dinv, c.inv2);
+    const Fr b = c.beta_point(c.chal + cw + (int)ln, c.chal + cv, (int)(l1 + l3));
+    if (!fr_eq(mulx(b, fr_sub(mulx(dinv, f[0]), mulx(f[1], f[2]))), claim)) return 1808;
+    return 0;
+}
+
 // A whole proof: a window ("ZKAG": g_t form; "ZKAF": f_t form for the matrix products; "ZKAL": the claims chained)
-// or a parameter update ("ZKUP").  The context's transcript is
+// a parameter update ("ZKUP") or a matrix product in the general aggregated form ("ZKGA").  The context's transcript is
 // the one before the proof and, on return, after it; c.chal / c.n_chal every challenge in draw order; c.inv2 and
 // c.inv6 are 1/2 and 1/6 (checked here).
 template <class C>
@@ -921,6 +965,12 @@ VF_HD int aggregate(C& c, const uint8_t* proof, size_t len) {
     const uint32_t magic = rd_u32(r), L = rd_u32(r), B = rd_u32(r), width = rd_u32(r), T = rd_u32(r), Q = rd_u32(r), R = rd_u32(r);
     const uint32_t pad = rd_u32(r);
     if (r.bad) return 100;
+    if (magic == ZKGA_MAGIC) {   // "ZKGA", log2 N, log2 D1, log2 D3, log2 D2, 0, 0, 0
+        if (Q != 0 || R != 0 || pad != 0) return 100;
+        const int rc = matmul_general(c, r, L, B, width, T);
+        if (rc) return rc;
+        return r.at == len ? 0 : 103;
+    }
     if (magic == ZKUP_MAGIC) {   // "ZKUP", log2 D, Q, R, 0, 0, 0, 0
         if (T != 0 || Q != 0 || R != 0 || pad != 0) return 100;
         const int rc = update(c, r, L, B, width);

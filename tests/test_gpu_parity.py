@@ -224,6 +224,9 @@ def test_sumcheck_matmul_general(lib, ctx, n, d1, d2, d3, kind):
     assert tr.digest() == ots.digest()
     finals, _ = P.matmul_general_verify(got["proof"], n, d1, d2, d3, OracleTranscript(8))
     assert finals == got["claims"]
+    tv = lib.Transcript(8)
+    ver = lib.aggregate_verify(ctx, got["proof"], tv)                 # the library's verifier, on the GPU
+    assert ver["verdict"] == 0 and ver["points"] == ots.challenges and tv.digest() == ots.digest()
 
 
 @pytest.mark.gpu
@@ -241,6 +244,7 @@ def test_sumcheck_matmul_general_wrong_product_is_rejected(lib, ctx):
     got = lib.sumcheck_matmul_general(ctx, a, b, c, lib.Transcript(8))
     with pytest.raises(AssertionError):
         P.matmul_general_verify(got["proof"], n, d1, d2, d3, OracleTranscript(8))
+    assert lib.aggregate_verify(ctx, got["proof"], lib.Transcript(8))["verdict"] != 0
 
 
 @pytest.mark.gpu
