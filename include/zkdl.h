@@ -395,15 +395,16 @@ int aggregate_prove(zkdl_ctx* ctx, const zkdl_fcnn_witness* w, zkdl_transcript* 
  * so the rounding is proved by zkReLU's forward half (App. A) on the stack Zu = [G_W; -G_W]:
  *   1. p is drawn over the D entries; the prover claims a0 = Au~(0,p), a1 = Au~(1,p), Au = ReLU(rescale(Zu));
  *      U~(p) = a0 - a1 is the value the verifier compares with W~(p) - W_next~(p);
- *   2. the two claims on Au are merged into one, Au~(v_n, v) (as claims_merge_stack_prove on [2, D]);
- *   3. u_Z is drawn over the 1 + log2 D variables of Zu and zkReLU runs at the given points u_A = (v_n, v),
+ *   2. a multilinear extension is linear in each coordinate, so the two claims lie on a line: rho is drawn after
+ *      they are absorbed and Au~(rho, p) = (1 - rho) a0 + rho a1 is the one claim that stands for both;
+ *   3. u_Z is drawn over the 1 + log2 D variables of Zu and zkReLU runs at the given points u_A = (rho, p),
  *      u_Z (as zkrelu_prove_at inside a larger proof: mode 2); its claim on Zu gives
  *      G_W~(u_Z[1:]) = Zu~(u_Z) / (1 - 2 u_Z[0]).
  * claims_out (ZKDL_UPDATE_NCLAIMS entries, may be NULL): U at p, GW at u_Z[1:], AUX (the bits of Zu) at zkReLU's
  * merged point; segments index points_out as in aggregate_prove.  points_out: every challenge in draw order,
  * with the three copied points of zkReLU (u_A, and u_Z twice for the unused backward side) after u_Z.
- * Transcript: header "update" (log2 D, Q, R); draw p; "merge_stack" (2, D, 2) and the merge; draw u_Z; zkReLU.
- * Proof: "ZKUP", log2 D, Q, R, 0, 0, 0, 0; a "ZKMS" block; a "ZKRL" block. */
+ * Transcript: header "update" (log2 D, Q, R); draw p; "c" a0, a1; one draw of rho and u_Z; zkReLU.
+ * Proof: "ZKUP", log2 D, Q, R, 0, 0, 0, 0; a0, a1; a "ZKRL" block. */
 #define ZKDL_UPDATE_NCLAIMS 3
 int update_prove(zkdl_ctx* ctx, const int64_t* GW, uint64_t D, int Q, int R, int src_on_device, zkdl_transcript* tr,
                  uint8_t* proof, size_t* proof_len, zkdl_fr* points_out, size_t* npoints, zkdl_claim* claims_out,

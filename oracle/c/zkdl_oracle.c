@@ -1927,8 +1927,8 @@ int zko_stack_merge_prove(const uint8_t* x, uint64_t n, uint64_t d, int K, const
 }
 
 /* Proof of the parameter update (Sec. 5, Example FCNN, last item; the rounding by zkReLU, Sec. 3.1 and App. A),
- * the steps of the first tier's update_prove in the same order: header, p, Au = ReLU(rescale([G; -G])), the
- * merge of the two claims Au~(0, p), Au~(1, p) on the stack [2, D], u_Z, zkReLU at the given points. */
+ * the steps of the first tier's update_prove in the same order: header, p, Au = ReLU(rescale([G; -G])), the two
+ * claims Au~(0, p), Au~(1, p), rho and u_Z, zkReLU at the given points u_A = (rho, p), u_Z. */
 int zko_update_prove(const int64_t* gw, uint64_t D, int q, int rb, zko_ts* ts, uint8_t* proof, uint64_t cap,
                      uint64_t* proof_len) {
     init_mu();
@@ -1942,9 +1942,11 @@ int zko_update_prove(const int64_t* gw, uint64_t D, int q, int rb, zko_ts* ts, u
     ts_draw(ts, ld, p);
     int64_t* zu = (int64_t*)malloc(sizeof(int64_t) * 2 * D);
     fe* au = (fe*)malloc(sizeof(fe) * 2 * D);
-    if (!zu || !au) {
+    fe* bp = beta_table(p, ld);
+    if (!zu || !au || !bp) {
         free(zu);
         free(au);
+        free(bp);
         return ZKO_ENOMEM;
     }
     int rc = 0;
@@ -1958,32 +1960,32 @@ int zko_update_prove(const int64_t* gw, uint64_t D, int q, int rb, zko_ts* ts, u
             const int64_t zp = (zu[i] + half) >> rb; /* zkReLU's rescaling: round half up */
             au[i] = fe_from_u64(zp > 0 ? (uint64_t)zp : 0);
         }
-        fe pt0[41], pt1[41];
-        pt0[0] = fe_from_u64(0);
-        pt1[0] = fe_from_u64(1);
-        for (int c = 0; c < ld; ++c) pt0[1 + c] = pt1[1 + c] = p[c];
-        const fe* pts[2] = {pt0, pt1};
+        fe a[2];
+        for (int k = 0; k < 2; ++k) { /* Au~(k, p) = sum_x beta~(p, x) Au[k, x] */
+            fe acc = fe_from_u64(0);
+            for (uint64_t x = 0; x < D; ++x) acc = fe_add(acc, fe_mul(bp[x], au[(uint64_t)k * D + x]));
+            a[k] = acc;
+        }
+        ts_absorb_fe(ts, "c", a, 2);
+        fe drawn[42];
+        ts_draw(ts, 1 + li, drawn);
         wbuf wb = {proof, (size_t)cap, 0};
         wb_u32(&wb, 0x50554B5Au); /* "ZKUP" */
         wb_u32(&wb, (uint32_t)ld);
         wb_u32(&wb, (uint32_t)q);
         wb_u32(&wb, (uint32_t)rb);
         for (int k = 0; k < 4; ++k) wb_u32(&wb, 0);
-        ms_info ms;
-        rc = stack_merge_core(au, 2, D, 2, pts, ts, 0, &wb, &ms);
+        wb_fe(&wb, a[0]);
+        wb_fe(&wb, a[1]);
+        fe* four = (fe*)malloc(sizeof(fe) * 4 * (size_t)li);
+        if (!four) rc = ZKO_ENOMEM;
         if (!rc) {
-            fe uz[40];
-            ts_draw(ts, li, uz);
-            fe* four = (fe*)malloc(sizeof(fe) * 4 * (size_t)li);
-            if (!four) rc = ZKO_ENOMEM;
-            if (!rc) {
-                for (int c = 0; c < li; ++c) four[c] = four[2 * li + c] = four[3 * li + c] = uz[c];
-                four[li] = ms.vn[0];
-                for (int c = 0; c < ld; ++c) four[li + 1 + c] = ms.v[c];
-                zk_info zi;
-                rc = zkrelu_core(zu, 0, 2 * D, q, rb, ts, four, 0, &wb, &zi);
-                free(four);
-            }
+            for (int c = 0; c < li; ++c) four[c] = four[2 * li + c] = four[3 * li + c] = drawn[1 + c];
+            four[li] = drawn[0];
+            for (int c = 0; c < ld; ++c) four[li + 1 + c] = p[c];
+            zk_info zi;
+            rc = zkrelu_core(zu, 0, 2 * D, q, rb, ts, four, 0, &wb, &zi);
+            free(four);
         }
         if (!rc) {
             *proof_len = wb.len;
@@ -1992,6 +1994,7 @@ int zko_update_prove(const int64_t* gw, uint64_t D, int q, int rb, zko_ts* ts, u
     }
     free(zu);
     free(au);
+    free(bp);
     return rc;
 }
 

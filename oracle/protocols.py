@@ -1116,8 +1116,11 @@ def aggregate_linked_verify(buf, ts):
 #   1. p drawn over the D entries; the prover claims a0 = Au~(0, p), a1 = Au~(1, p) for
 #      Au = ReLU(rescale(Zu)) = [U+; U-]; U~(p) = a0 - a1 is what the verifier compares with
 #      W~(p) - W_next~(p) (two openings of commitments, or claims of other sumchecks);
-#   2. the two claims on Au are merged into one, Au~(v_n, v) (stack_merge_prove on [2, D]);
-#   3. u_Z drawn over the 1 + log D variables of Zu; zkReLU at the given points u_A = (v_n, v)
+#   2. a multilinear extension is linear in each coordinate (Eq. multilinear-extension), so the two
+#      claims lie on a line: with rho drawn after they are absorbed, Au~(rho, p) = (1 - rho) a0 + rho a1
+#      is ONE claim that stands for both (wrong a0 or a1 give a different line, which agrees with the
+#      true one at one rho at most);
+#   3. u_Z drawn over the 1 + log D variables of Zu; zkReLU at the given points u_A = (rho, p)
 #      and u_Z proves that Au and Zu are what their bit decompositions say; its claim on Zu is
 #      Zu~(u_Z) = (1 - 2 u_Z[0]) G_W~(u_Z[1:]), a claim on the (committed) gradients.
 # --------------------------------------------------------------------------
@@ -1131,15 +1134,11 @@ def sround(g, r_bits):
     return mag if g >= 0 else -mag
 
 
-def _sc_block_len(rounds, degree, n_finals):
-    return 16 + 32 + rounds * (degree + 1) * 32 + 32 * n_finals
-
-
 def update_prove(gw, q, r_bits, ts):
     """gw: D = 2^k signed integers below 2^(q + r_bits - 1) in magnitude (q + r_bits <= 63).
-    Transcript: header "update" (log D, Q, R); draw p; the stack merge ("merge_stack" words
-    2, D, 2, its claims, coefficients and two sumchecks); draw u_Z; zkReLU at given points
-    (mode 2).  Proof: "ZKUP", log D, Q, R, 0, 0, 0, 0; the "ZKMS" block; the "ZKRL" block."""
+    Transcript: header "update" (log D, Q, R); draw p; "c" the two claims a0, a1; one draw of
+    rho and u_Z (2 + log D elements); zkReLU at given points (mode 2).
+    Proof: "ZKUP", log D, Q, R, 0, 0, 0, 0; a0, a1; the "ZKRL" block."""
     d = len(gw)
     ld = ilog2(d)
     assert q + r_bits <= 63
@@ -1148,13 +1147,15 @@ def update_prove(gw, q, r_bits, ts):
     zu = [int(g) for g in gw] + [-int(g) for g in gw]
     wit = zkrelu_witness(zu, [0] * (2 * d), q, r_bits)
     au = [int(a) for a in wit["A"]]
-    ms_buf, ms = stack_merge_prove(fr_array(au).reshape(2, d), 2, d, [[0] + p, [1] + p], ts, bind_statement=False)
-    u_a = ms["vn"] + ms["v"]
-    u_z = ts.challenges_vec(1 + ld)
+    a0, a1 = mle_eval(fr_array(au[:d]), p), mle_eval(fr_array(au[d:]), p)
+    ts.absorb_fr(b"c", [a0, a1])
+    drawn = ts.challenges_vec(2 + ld)
+    rho, u_z = drawn[0], drawn[1:]
+    u_a = [rho] + p
     zk_buf, zk = zkrelu_prove(zu, None, q, r_bits, ts, points=(u_z, u_a, u_z, u_z), bind_points=False)
-    assert zk["c_in"][1] == ms["outer"].finals[1], "zkReLU does not start from the merged claim on Au"
+    assert zk["c_in"][1] == ((1 - rho) * a0 + rho * a1) % R_MOD, "zkReLU does not start from the claim on the line"
     head = struct.pack("<IIIIIIII", ZKUP_MAGIC, ld, q, r_bits, 0, 0, 0, 0)
-    return head + ms_buf + zk_buf, dict(p=p, a=ms["claims"], u_a=u_a, u_z=u_z, merge=ms, zkrelu=zk)
+    return head + to_le(a0) + to_le(a1) + zk_buf, dict(p=p, a=[a0, a1], rho=rho, u_a=u_a, u_z=u_z, zkrelu=zk)
 
 
 def update_verify(buf, ld, q, r_bits, ts):
@@ -1162,19 +1163,19 @@ def update_verify(buf, ld, q, r_bits, ts):
     aux = zkReLU's one claim on the bit tensor of Zu."""
     magic, ld_, q_, r_, z0, z1, z2, z3 = struct.unpack_from("<IIIIIIII", buf, 0)
     assert magic == ZKUP_MAGIC and (ld_, q_, r_) == (ld, q, r_bits) and z0 == z1 == z2 == z3 == 0
-    d = 1 << ld
     ts.absorb_u32(b"update", [ld, q, r_bits])
     p = ts.challenges_vec(ld)
-    ms_len = 16 + 64 + _sc_block_len(1 + ld, 2, 2) + _sc_block_len(1, 2, 2)
-    claims, pt, au_claim = stack_merge_verify(buf[32:32 + ms_len], 2, d, [[0] + p, [1] + p], ts, bind_statement=False)
-    u_z = ts.challenges_vec(1 + ld)
-    end, zk = zkrelu_verify(buf, ts, off=32 + ms_len, points=(u_z, pt, u_z, u_z))
+    a0, a1 = from_le(buf[32:64]), from_le(buf[64:96])
+    ts.absorb_fr(b"c", [a0, a1])
+    drawn = ts.challenges_vec(2 + ld)
+    rho, u_z = drawn[0], drawn[1:]
+    end, zk = zkrelu_verify(buf, ts, off=96, points=(u_z, [rho] + p, u_z, u_z))
     assert end == len(buf), "trailing bytes"
-    li, q2, r2, has_ga = struct.unpack_from("<IIII", buf, 32 + ms_len + 4)
+    li, q2, r2, has_ga = struct.unpack_from("<IIII", buf, 96 + 4)
     assert (li, q2, r2, has_ga) == (1 + ld, q, r_bits, 0)
-    assert zk["c_in"][1] == au_claim, "zkReLU's claim on Au is not the merged one"
+    assert zk["c_in"][1] == ((1 - rho) * a0 + rho * a1) % R_MOD, "zkReLU's claim on Au is not the one on the line"
     assert zk["c_in"][2] == 0 and zk["c_in"][3] == 0
     den = (1 - 2 * u_z[0]) % R_MOD
     assert den != 0
     gw_val = zk["c_in"][0] * pow(den, -1, R_MOD) % R_MOD
-    return dict(u=(p, (claims[0] - claims[1]) % R_MOD), gw=(u_z[1:], gw_val), aux=zk["aux_claim"])
+    return dict(u=(p, (a0 - a1) % R_MOD), gw=(u_z[1:], gw_val), aux=zk["aux_claim"])

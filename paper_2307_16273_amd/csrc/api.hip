@@ -1492,7 +1492,6 @@ extern "C" int zkrelu_prove_at(zkdl_ctx* ctx, const int64_t* Z, const int64_t* G
 
 // ---- proof of the parameter update ------------------------------------------------------------
 static const uint32_t ZKUP_MAGIC = 0x50554B5Au;
-static const uint32_t ZKMS_MAGIC_UP = 0x534D4B5Au;
 
 // zu = [g; -g], au = ReLU(rescale(zu)) with zkReLU's rescaling (round half up): au = [U+; U-]
 __global__ __launch_bounds__(ZK_BLOCK) void k_update_witness(const int64_t* g, uint64_t D, int r_bits, int64_t* zu,
@@ -1566,22 +1565,19 @@ extern "C" int update_prove(zkdl_ctx* ctx, const int64_t* GW, uint64_t D, int Q,
     while ((1 << lj) < Q + R) ++lj;
     rc = call_begin(ctx, tr);
     if (rc != ZKDL_OK) return rc;
-    // the coordinates 0 and 1 of the stack axis of Au, as canonical bytes
-    uint8_t consts[64] = {};
-    consts[32] = 1;
-    void *d_const = nullptr, *gs = nullptr;
-    rc = upload_bytes(ctx, consts, sizeof consts, &d_const);
+    void* gs = nullptr;
     const int64_t* gd = GW;
-    if (rc == ZKDL_OK && !src_on_device) {
+    if (!src_on_device) {
         rc = stage_ints(ctx, GW, D, &gs);
         gd = (const int64_t*)gs;
     }
     int64_t* zu = (int64_t*)zk_alloc(ctx, 2 * D * 8);
     int64_t* au = (int64_t*)zk_alloc(ctx, 2 * D * 8);
-    if (rc == ZKDL_OK && (!zu || !au)) rc = ZKDL_ENOMEM;
-    std::vector<void*> keep;
-    int cp = 0, c_ms = 0, cz = 0;
-    size_t p_ms = 0, pz = 0, pz_end = 0;
+    void* bmem = zk_alloc(ctx, (D + 2) * 32);
+    if (rc == ZKDL_OK && (!zu || !au || !bmem)) rc = ZKDL_ENOMEM;
+    if (rc == ZKDL_OK && ctx->n_chal + ld + 1 + 4 * li > ZK_MAX_CHAL) rc = ZKDL_EINVAL;
+    int cp = 0, c_rho = 0, cz = 0;
+    size_t p_claims = 0, pz = 0, pz_end = 0;
     if (rc == ZKDL_OK) {
         const uint64_t blocks = (D + ZK_BLOCK - 1) / ZK_BLOCK;
         hipLaunchKernelGGL(k_update_witness, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(ZK_BLOCK), 0, ctx->stream,
@@ -1593,50 +1589,33 @@ extern "C" int update_prove(zkdl_ctx* ctx, const int64_t* GW, uint64_t D, int Q,
         cp = ctx->n_chal;
         zk_launch_draw(ctx, cp, ld);
         ctx->n_chal += ld;
-        // the two claims Au~(0, p), Au~(1, p) become one: a merge on the stack [2, D]
-        const int at0 = ZK_MAX_CHAL - ZK_CHAL_SET_MAX, at1 = at0 + ZK_CHAL_SET_MAX / 2;
-        ChalIdx pi = {};
-        for (int i = 0; i < ld; ++i) pi.v[i] = (int16_t)(cp + i);
-        zk_launch_chal_set(ctx, at0, 1, (const uint8_t*)d_const, nullptr);
-        zk_launch_chal_set(ctx, at1, 1, (const uint8_t*)d_const + 32, nullptr);
-        if (ld > 0) {
-            zk_launch_chal_set(ctx, at0 + 1, ld, nullptr, &pi);
-            zk_launch_chal_set(ctx, at1 + 1, ld, nullptr, &pi);
+        // the two claims Au~(0, p), Au~(1, p): the rows of Au [2, D] against beta~(p, .)
+        const FrTab bp = make_tab(bmem, D), two = make_tab((uint32_t*)bmem + 8 * D, 2);
+        rc = zk_build_beta(ctx, ctx->dev->chal + cp, ld, bp);
+        if (rc == ZKDL_OK) rc = zk_partial_eval(ctx, TK_I64, au, 2, D, 1, bp, two);
+        if (rc == ZKDL_OK) {
+            const int claims_scal = 8;
+            zk_launch_soa_to_aos(ctx, two, 2, ctx->dev->scal + claims_scal);
+            // absorbed, then rho and u_Z in one draw: u_Z stands where zkReLU's first given point does
+            p_claims = ctx->proof_len;
+            c_rho = ctx->n_chal;
+            zk_launch_absorb_claims(ctx, claims_scal, 2, (uint32_t)p_claims, c_rho, 1 + li);
+            ctx->proof_len += 64;
+            ctx->n_chal += 1;
+            cz = ctx->n_chal;
+            // u_A = (rho, p): the two claims lie on a line in the stack coordinate; the backward points
+            // (unused: there is no gradient side) are copies of u_Z
+            ChalIdx idx = {};
+            int at = 0;
+            idx.v[at++] = (int16_t)c_rho;
+            for (int i = 0; i < ld; ++i) idx.v[at++] = (int16_t)(cp + i);
+            for (int rep = 0; rep < 2; ++rep)
+                for (int i = 0; i < li; ++i) idx.v[at++] = (int16_t)(cz + i);
+            zk_launch_chal_set(ctx, cz + li, 3 * li, nullptr, &idx);
+            pz = ctx->proof_len;
+            rc = enqueue_zkrelu(ctx, zu, nullptr, 2 * D, Q, R, 2, nullptr);
+            pz_end = ctx->proof_len;
         }
-        uint32_t hw3[3] = {2, (uint32_t)D, 2};
-        zk_absorb_words(ctx, "merge_stack", hw3, 3);
-        uint32_t mh[4] = {ZKMS_MAGIC_UP, 2, (uint32_t)D, 2};
-        zk_write_proof_words(ctx, mh, 4);
-        p_ms = ctx->proof_len;
-        c_ms = ctx->n_chal;
-        StackMergeJob job = {};
-        job.K = 2;
-        job.point[0] = ctx->dev->chal + at0;
-        job.point[1] = ctx->dev->chal + at1;
-        job.kind = TK_I64;
-        job.X = au;
-        job.N = 2;
-        job.rows = (uint64_t)1 << (ld / 2);
-        job.cols = (uint64_t)1 << (ld - ld / 2);
-        rc = zk_stack_merge(ctx, job, keep);
-    }
-    if (rc == ZKDL_OK && ctx->n_chal + 4 * li > ZK_MAX_CHAL - ZK_CHAL_SET_MAX) rc = ZKDL_EINVAL;
-    if (rc == ZKDL_OK) {
-        // zkReLU on Zu = [G_W; -G_W]: u_Z drawn where the first given point stands, u_A = the merged point
-        // (v_n, v), the two backward points (unused: there is no gradient side) copies of u_Z
-        const int c_v = c_ms + 2 + 1, c_vn = c_v + ld;   // merge: 2 coefficients, rho, v (ld), then v_n
-        cz = ctx->n_chal;
-        zk_launch_draw(ctx, cz, li);
-        ChalIdx idx = {};
-        int at = 0;
-        idx.v[at++] = (int16_t)c_vn;
-        for (int i = 0; i < ld; ++i) idx.v[at++] = (int16_t)(c_v + i);
-        for (int rep = 0; rep < 2; ++rep)
-            for (int i = 0; i < li; ++i) idx.v[at++] = (int16_t)(cz + i);
-        zk_launch_chal_set(ctx, cz + li, 3 * li, nullptr, &idx);
-        pz = ctx->proof_len;
-        rc = enqueue_zkrelu(ctx, zu, nullptr, 2 * D, Q, R, 2, nullptr);
-        pz_end = ctx->proof_len;
     }
     int rc2 = call_end(ctx, tr, rc, proof, proof_len, points_out, npoints, nullptr, 0, nullptr);
     if (rc == ZKDL_OK && rc2 == ZKDL_OK && claims_out) {
@@ -1644,7 +1623,7 @@ extern "C" int update_prove(zkdl_ctx* ctx, const int64_t* GW, uint64_t D, int Q,
         const uint8_t* chal_le = ((const DevState*)ctx->host_stage)->chal_le;
         ClaimList cl = {claims_out, 0, sp};
         // U~(p) = Au~(0, p) - Au~(1, p)
-        const Fr u = fr_from_mont(fr_sub(fr_from_le32(sp + p_ms), fr_from_le32(sp + p_ms + 32)));
+        const Fr u = fr_from_mont(fr_sub(fr_from_le32(sp + p_claims), fr_from_le32(sp + p_claims + 32)));
         cl.add(ZKDL_T_U, {{cp, ld}}, (const uint8_t*)u.v);
         // Zu~(u_Z) = (1 - 2 u_Z[0]) G_W~(u_Z[1:])
         const Fr u0 = fr_from_le32(chal_le + 32 * (size_t)cz);
@@ -1657,11 +1636,10 @@ extern "C" int update_prove(zkdl_ctx* ctx, const int64_t* GW, uint64_t D, int Q,
         cl.add_at(ZKDL_T_AUX, {{c_vm, 1}, {c_v, li}, {c_vm + 1, lj}}, pz_end - 64);
         *nclaims = cl.n;
     }
-    for (void* p : keep) zk_free(ctx, p);
     zk_free(ctx, zu);
     zk_free(ctx, au);
+    zk_free(ctx, bmem);
     zk_free(ctx, gs);
-    zk_free(ctx, d_const);
     return rc != ZKDL_OK ? rc : rc2;
 }
 

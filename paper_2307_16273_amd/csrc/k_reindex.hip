@@ -29,14 +29,20 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_ri_claims(DevState* st, RiMaps m, 
     if (threadIdx.x == 0) st->scal[scal_base + k] = acc;
 }
 
-// absorbs the K claims under "c" (and writes them to the proof), draws r_0 .. r_{K-1}
+// absorbs the K claims under "c" (and writes them to the proof), then draws n_draw challenges
 __global__ __launch_bounds__(ZK_BLOCK) void k_ri_absorb(DevState* st, int scal_base, int K, uint32_t proof_off,
-                                                        int chal_base) {
+                                                        int chal_base, int n_draw) {
     __shared__ TsShared S;
     block_ts_load(S, st);
     block_absorb_frs(S, 'c', &st->scal[scal_base], K, (uint32_t*)(st->proof + proof_off));
-    block_challenges(S, st, chal_base, K);
+    block_challenges(S, st, chal_base, n_draw);
     block_ts_store(S, st);
+}
+
+void zk_launch_absorb_claims(zkdl_ctx* ctx, int scal_base, int K, uint32_t proof_off, int chal_base, int n_draw) {
+    zk_flush_frames(ctx);
+    hipLaunchKernelGGL(k_ri_absorb, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, scal_base, K, proof_off, chal_base,
+                       n_draw);
 }
 
 // P[i] = sum over the entries e of row i of the inverse maps of r_{k(e)} * beta_{k(e)}[j(e)];
@@ -92,7 +98,7 @@ int zk_reindex(zkdl_ctx* ctx, const ReindexJob& job, FrTab t, FrTab p, int ln, v
     hipLaunchKernelGGL(k_ri_claims, dim3(job.K), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, m, t, claims_scal);
     const int chal_base = ctx->n_chal;
     hipLaunchKernelGGL(k_ri_absorb, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, claims_scal, job.K,
-                       (uint32_t)ctx->proof_len, chal_base);
+                       (uint32_t)ctx->proof_len, chal_base, job.K);
     ctx->proof_len += 32 * (size_t)job.K;
     ctx->n_chal += job.K;
     const uint64_t n = (uint64_t)1 << ln;
@@ -166,7 +172,7 @@ int zk_merge(zkdl_ctx* ctx, int K, const FrTab* beta, FrTab x, FrTab p, int d, v
                        (const Fr*)ctx->partials, (int)nblk, claims_scal);
     const int chal_base = ctx->n_chal;
     hipLaunchKernelGGL(k_ri_absorb, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, claims_scal, K,
-                       (uint32_t)ctx->proof_len, chal_base);
+                       (uint32_t)ctx->proof_len, chal_base, K);
     ctx->proof_len += 32 * (size_t)K;
     ctx->n_chal += K;
     const unsigned wblk = (unsigned)(blocks < 4096 ? blocks : 4096);
@@ -261,7 +267,7 @@ int zk_stack_merge(zkdl_ctx* ctx, const StackMergeJob& job, std::vector<void*>& 
                        (const Fr*)ctx->partials, (int)nblk, claims_scal);
     const int chal_base = ctx->n_chal;
     hipLaunchKernelGGL(k_ri_absorb, dim3(1), dim3(ZK_BLOCK), 0, ctx->stream, ctx->dev, claims_scal, K,
-                       (uint32_t)ctx->proof_len, chal_base);
+                       (uint32_t)ctx->proof_len, chal_base, K);
     ctx->proof_len += 32 * (size_t)K;
     ctx->n_chal += K;
     const uint64_t sblocks = ((uint64_t)K2 * D + ZK_BLOCK - 1) / ZK_BLOCK;

@@ -866,9 +866,10 @@ VF_NI int aggregate_linked(C& c, Reader& r, uint32_t L, uint32_t B, uint32_t wid
     return 0;
 }
 
-// The proof of the parameter update ("ZKUP"; Sec. 5, Example FCNN, last item): the two claims Au~(0, p), Au~(1, p)
-// merged on the stack [2, D], then zkReLU's forward half on [G_W; -G_W] at u_A = the merged point and a drawn u_Z.
-// Stages in the codes: 13 header, 14 the merge, 15 / 16 zkReLU, 17 the links.
+// The proof of the parameter update ("ZKUP"; Sec. 5, Example FCNN, last item): the two claims a0 = Au~(0, p),
+// a1 = Au~(1, p), the point rho on the line through them, then zkReLU's forward half on [G_W; -G_W] at
+// u_A = (rho, p) and a drawn u_Z, whose claim on Au must be (1 - rho) a0 + rho a1.
+// Stages in the codes: 13 header and claims, 15 / 16 zkReLU, 17 the links.
 template <class C>
 VF_NI int update(C& c, Reader& r, uint32_t ld, uint32_t Q, uint32_t R) {
     if (ld > 30 || Q + R > 63) return 1301;
@@ -876,29 +877,28 @@ VF_NI int update(C& c, Reader& r, uint32_t ld, uint32_t Q, uint32_t R) {
     c.absorb_words("update", 6, words, 3);
     const int cp = c.draw((int)ld);
     if (c.overflow) return 1302;
-    Fr p0[MAX_PT], p1[MAX_PT];
-    p0[0] = fr_zero();
-    p1[0] = fr_one();
-    for (uint32_t k = 0; k < ld; ++k) p0[1 + k] = p1[1 + k] = c.chal[cp + (int)k];
-    const Fr* pts[2] = {p0, p1};
-    Fr cl[2], left;
-    int cvn, cv;
-    int rc = stack_merge(c, r, 2, (uint64_t)1 << ld, 2, pts, cl, &cvn, &cv, &left);
-    if (rc) return 1400 + rc;
+    const uint8_t* src = nullptr;
+    Fr a[2];
+    c.rd_elems(r, 2, a, &src);
+    if (r.bad) return 1303;
+    c.absorb_elems('c', src, 2);
     const int li = (int)ld + 1;
-    const int cz = c.draw(li);
+    const int c_rho = c.draw(1 + li);
     if (c.overflow) return 1302;
+    const int cz = c_rho + 1;
     Fr given[4 * MAX_PT];
     int at = 0;
     put_coords(given, &at, c.chal + cz, li);
-    put_coords(given, &at, c.chal + cvn, 1), put_coords(given, &at, c.chal + cv, (int)ld);
+    put_coords(given, &at, c.chal + c_rho, 1), put_coords(given, &at, c.chal + cp, (int)ld);
     put_coords(given, &at, c.chal + cz, li);
     put_coords(given, &at, c.chal + cz, li);
     ZkOut zk;
-    rc = zkrelu(c, r, li, Q, R, given, &zk);
+    const int rc = zkrelu(c, r, li, Q, R, given, &zk);
     if (rc) return (rc >= 100 ? 1600 + rc - 100 : 1500 + rc);
     if (zk.has_ga != 0) return 1701;
-    if (!fr_eq(zk.c_in[1], left)) return 1702;   // zkReLU starts from the merged claim on Au
+    const Fr rho = c.chal[c_rho];
+    const Fr line = fr_add(a[0], mulx(rho, fr_sub(a[1], a[0])));
+    if (!fr_eq(zk.c_in[1], line)) return 1702;   // zkReLU starts from the claim on the line
     const Fr zero = fr_zero();
     if (!fr_eq(zk.c_in[2], zero) || !fr_eq(zk.c_in[3], zero)) return 1703;
     return 0;

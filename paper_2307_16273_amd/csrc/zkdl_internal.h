@@ -194,6 +194,10 @@ int zk_reindex(zkdl_ctx* ctx, const ReindexJob& job, FrTab t, FrTab p, int ln, v
 void zk_launch_layer_maps(zkdl_ctx* ctx, uint32_t N, uint32_t L, int with_ident, int32_t* maps, uint32_t* row_off,
                           uint32_t* ent);
 
+// claims st->scal[scal_base .. + K) absorbed under "c" and written to the proof at proof_off, then n_draw challenges
+// drawn into chal[chal_base ..)
+void zk_launch_absorb_claims(zkdl_ctx* ctx, int scal_base, int K, uint32_t proof_off, int chal_base, int n_draw);
+
 // K claims X~(p_k) on the table x (2^d entries) -> one: the claims -> scal[8 ..), absorbed and written
 // to the proof; K coefficients drawn; P = sum_k r_k beta[k] built into p; product sumcheck on (p, x),
 // finals at scal[0], scal[1]

@@ -75,11 +75,14 @@ def test_update_claims_are_the_definitions(d, q, r_bits):
     wit = P.zkrelu_witness(zu, [0] * (2 * d), q, r_bits)
     aux = np.concatenate([fr_array(wit["aux0"]), fr_array(wit["aux1"])])
     assert out["aux"]["value"] == mle_eval(aux, out["aux"]["point"])
-    # proof size: header, the merge (2 claims, 1 + log D + 1 rounds), zkReLU on 2 D rows
+    # the two claims lie on a line in the stack coordinate: the one claim zkReLU starts from is Au~(rho, p)
+    au = [max(0, x) for x in u] + [max(0, -x) for x in u]
+    assert info["zkrelu"]["c_in"][1] == mle_eval(fr_array(au), [info["rho"]] + p)
+    assert info["zkrelu"]["c_in"][1] == ((1 - info["rho"]) * info["a"][0] + info["rho"] * info["a"][1]) % R_MOD
+    # proof size: header, the two claims, zkReLU on 2 D rows
     lj = ilog2(wit["j_pad"])
-    ms = 16 + 64 + (16 + 32 + (1 + ld) * 96 + 64) + (16 + 32 + 96 + 64)
     zk = 32 + 128 + (16 + 32 + (1 + ld + lj) * 128 + 96) + (16 + 32 + (1 + lj) * 96 + 64)
-    assert len(buf) == 32 + ms + zk
+    assert len(buf) == 32 + 64 + zk
 
 
 def test_update_closes_a_step_of_sgd():
@@ -109,7 +112,7 @@ def test_update_rejects_out_of_range_and_tampering():
     buf, _ = P.update_prove(g, 5, 3, Transcript(2))
     P.update_verify(buf, 2, 5, 3, Transcript(2))
     rng = np.random.default_rng(0)
-    elems = [o for o in range(48, len(buf) - 31, 32)]
+    elems = [32, 64] + [o for o in range(96 + 32, len(buf) - 31, 32)]
     for off in rng.choice(elems, 24, replace=False):
         bad = bytearray(buf)
         bad[off + 3] ^= 0x10
