@@ -1009,6 +1009,10 @@ def test_gpu_verifier_agrees_with_the_oracles(lib, ctx, layers, width, batch, st
         assert on_gpu["verdict"] != 0 and on_gpu["verdict"] == on_cpu["verdict"]
         assert t1.digest() == before
     assert lib.aggregate_verify(ctx, proof, lib.Transcript(37))["verdict"] != 0     # another transcript
+    # a buffer too long to be staged in LDS is read from device memory: the same verdict (trailing bytes)
+    long_buf = proof + bytes(40000)
+    assert lib.aggregate_verify(ctx, long_buf, lib.Transcript(36))["verdict"] == \
+        lib.aggregate_verify(None, long_buf, lib.Transcript(36))["verdict"] == 103
 
 
 @pytest.mark.parametrize("layers,width,batch,steps", [(2, 8, 4, 2), (4, 32, 8, 1), (1, 16, 2, 1), (8, 16, 4, 16)])
