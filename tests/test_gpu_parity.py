@@ -196,6 +196,8 @@ def test_sumcheck_matmul_ft(lib, ctx, n, d1, d2, d3, t0, t1, kind):
     (16, 4, 64, 16, "fr"),
     (64, 8, 8, 8, "int"),          # six stack rounds
     (2, 2, 1024, 2, "int"),        # tables of the j rounds longer than a block
+    (8, 32, 32, 16, "int"),        # 2^17 terms: several blocks in the stack rounds, every phase longer than a wave
+    (16, 64, 64, 32, "int"),       # 2^21 terms
 ])
 def test_sumcheck_matmul_general(lib, ctx, n, d1, d2, d3, kind):
     """The general aggregated form on the three stacks: proof bytes, challenges, finals and transcript
