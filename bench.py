@@ -281,6 +281,16 @@ def main():
             xv = zk.tensor_wrap_int(ctx, flat)
             cm_med, _ = timed(lambda: zk.hyrax_commit(ctx, key, xv), 3)
             out["config"]["commit_ms_%s_stack_2p%d" % (nm, mm)] = 1e3 * cm_med
+            if nm == "A":   # the proof of evaluation at a random point and the verifier's two sums on the GPU
+                prng = np.random.default_rng(CONFIG_SEED + 34)
+                pt = [int.from_bytes(prng.bytes(31), "little") for _ in range(mm)]
+                coms = zk.hyrax_commit(ctx, key, xv)
+                op_med, _ = timed(lambda: zk.hyrax_open(ctx, xv, None, pt), 3)
+                t_row, _, y_val = zk.hyrax_open(ctx, xv, None, pt)
+                hv_med, _ = timed(lambda: zk.hyrax_verify(ctx, key, coms, pt, t_row, None, y_val), 3)
+                assert zk.hyrax_verify(ctx, key, coms, pt, t_row, None, y_val)[0] == 0
+                out["config"]["open_ms_A_stack_2p%d" % mm] = 1e3 * op_med
+                out["config"]["open_verify_ms_A_stack_2p%d" % mm] = 1e3 * hv_med
             key.close()
         ag_med, ag_min = timed(lambda: zk.aggregate_prove(ctx, dw, zk.Transcript(CONFIG_SEED + 3)), 5)
         out["config"]["proof_ms_batch64_8layer_step"] = 1e3 * ag_med

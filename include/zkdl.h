@@ -508,6 +508,19 @@ int hyrax_commit(zkdl_ctx* ctx, const zkdl_commit_key* key, const zkdl_tensor* X
  * checks Commit(T; rho*) against the result and y against T.  X: any tensor of 2^m entries. */
 int hyrax_open(zkdl_ctx* ctx, const zkdl_tensor* X, const zkdl_fr* blind, const zkdl_fr* point, size_t npoint,
                zkdl_fr* T_out, zkdl_fr* rho_out, zkdl_fr* y_out);
+
+/* hyrax_verify: the verifier's side of that proof of evaluation (Sec. 2.3, the homomorphism; Protocol zkdl, the
+ * proof-of-evaluation line): C* = sum_j beta~(v_row, j) C_j over the nrows row commitments (host, 96 bytes
+ * each), Commit(T; rho*) on the key's generators, and <T, beta~(v_col, .)> against y.  point: npoint = log2 nrows
+ * + log2 C canonical elements, row coordinates first; T: C elements; rho: rho* or NULL for zero blinding.
+ * *verdict = 0 accepted, 1 malformed input (an element not below r, a commitment not on the curve), 2 the opened
+ * row does not match the combined commitment, 3 wrong evaluation.  combined_out (may be NULL): C* as 96 bytes.
+ * Both sums run on the GPU, one lane per term (double-and-add over the 255-bit scalar), the weights and the
+ * inner product on the host. */
+int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uint8_t* commitments, size_t nrows,
+                 const zkdl_fr* point, size_t npoint, const zkdl_fr* T, const zkdl_fr* rho, const zkdl_fr* y,
+                 int* verdict, uint8_t* combined_out);
+
 /* Re-derives the constants of the base-field arithmetic on the host; ZKDL_OK if they match. */
 int zkdl_commit_selfcheck(void);
 

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "zkdl_transcript_challenge", "zkdl_transcript_digest",
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
-    "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_matmul_general", "update_prove", "sumcheck_hadamard",
+    "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_matmul_general", "update_prove", "hyrax_verify", "sumcheck_hadamard",
     "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "aggregate_prove_ft", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read", "zkdl_selfbench",
     "zkdl_commit_key_create", "zkdl_commit_key_destroy", "zkdl_commit_key_generators", "hyrax_commit", "hyrax_open",
@@ -101,6 +101,7 @@ def load_library():
         "zkdl_commit_key_create": [vp, C.c_char_p, u64, i, pp], "zkdl_commit_key_destroy": [vp, vp],
         "zkdl_commit_key_generators": [vp, vp, u64, u64, vp],
         "hyrax_commit": [vp, vp, vp, vp, vp, psz], "hyrax_open": [vp, vp, vp, vp, sz, vp, vp, vp],
+        "hyrax_verify": [vp, vp, vp, sz, vp, sz, vp, vp, vp, vp, vp],
         "zkdl_commit_selfcheck": [],
         "aggregate_verify": [vp, vp, sz, vp, C.POINTER(i), vp, psz, vp, psz],
         "zkdl_host_aggregate_verify": [vp, sz, vp, C.POINTER(i), vp, psz, vp, psz],
@@ -549,6 +550,22 @@ def hyrax_open(ctx, x, blind, point):
     pb = C.create_string_buffer(_fr_bytes(point), max(32 * len(point), 1))
     _check(load_library().hyrax_open(ctx.handle, x.handle, bb, pb, len(point), t, rho, y), "hyrax_open", ctx)
     return _split_fr(t.raw, cols), int.from_bytes(rho.raw, "little"), int.from_bytes(y.raw, "little")
+
+
+def hyrax_verify(ctx, key, commitments, point, t, rho, y):
+    """commitments: list of 96-byte strings; t: the opened row; rho: rho* or None.  Returns (verdict, combined
+    commitment bytes); verdict 0 = accepted."""
+    rows = len(commitments)
+    cb = C.create_string_buffer(b"".join(commitments), 96 * rows)
+    pb = C.create_string_buffer(_fr_bytes(point), max(32 * len(point), 1))
+    tb = C.create_string_buffer(_fr_bytes(t), 32 * len(t))
+    rb = C.create_string_buffer(_fr_bytes([rho]), 32) if rho is not None else None
+    yb = C.create_string_buffer(_fr_bytes([y]), 32)
+    verdict = C.c_int(-1)
+    comb = C.create_string_buffer(96)
+    _check(load_library().hyrax_verify(ctx.handle, key.handle, cb, rows, pb, len(point), tb, rb, yb, C.byref(verdict), comb),
+           "hyrax_verify", ctx)
+    return verdict.value, comb.raw
 
 
 def commit_selfcheck():

@@ -267,23 +267,24 @@ struct FqMulInline {
 FQ_HD G1 g1_add(const G1& p, const G1& q) { return g1_add_with(p, q, FqMulInline()); }
 
 // doubling (Algorithm 9, a = 0)
-FQ_HD G1 g1_dbl(const G1& p) {
-    Fq t0 = fq_sqr(p.Y);
+template <class Mul>
+FQ_HD G1 g1_dbl_with(const G1& p, Mul mul) {
+    Fq t0 = mul(p.Y, p.Y);
     Fq z3 = fq_add(t0, t0);
     z3 = fq_add(z3, z3);
     z3 = fq_add(z3, z3);
-    Fq t1 = fq_mul(p.Y, p.Z);
-    Fq t2 = fq_mul12(fq_sqr(p.Z));
-    Fq x3 = fq_mul(t2, z3);
+    Fq t1 = mul(p.Y, p.Z);
+    Fq t2 = fq_mul12(mul(p.Z, p.Z));
+    Fq x3 = mul(t2, z3);
     Fq y3 = fq_add(t0, t2);
-    z3 = fq_mul(t1, z3);
+    z3 = mul(t1, z3);
     t1 = fq_add(t2, t2);
     t2 = fq_add(t1, t2);
     t0 = fq_sub(t0, t2);
-    y3 = fq_mul(t0, y3);
+    y3 = mul(t0, y3);
     y3 = fq_add(x3, y3);
-    t1 = fq_mul(p.X, p.Y);
-    x3 = fq_mul(t0, t1);
+    t1 = mul(p.X, p.Y);
+    x3 = mul(t0, t1);
     x3 = fq_add(x3, x3);
     G1 r;
     r.X = x3;
@@ -291,6 +292,8 @@ FQ_HD G1 g1_dbl(const G1& p) {
     r.Z = z3;
     return r;
 }
+
+FQ_HD G1 g1_dbl(const G1& p) { return g1_dbl_with(p, FqMulInline()); }
 
 FQ_HD G1 g1_neg(const G1& p) {
     G1 r = p;

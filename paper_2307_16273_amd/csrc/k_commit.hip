@@ -17,6 +17,7 @@
 // taken in any order.
 #include <string.h>
 #include <new>
+#include <vector>
 
 #include "zkdl_internal.h"
 #include "fq.cuh"
@@ -203,6 +204,79 @@ __global__ __launch_bounds__(64) void k_commit_affine(const G1* sums, uint64_t r
     g1_to_bytes(sums[row], out + row * 96);
 }
 
+// ---- the verifier's side of an opening: two sums of scalar multiples with full field elements as scalars ----
+__device__ inline G1 g1_dbl_ni(const G1& p) { return g1_dbl_with(p, FqMulOutOfLine()); }
+
+// 96 affine bytes -> Montgomery projective; *ok = false unless both coordinates are below q and the point is on
+// the curve (or the bytes are all zero: the identity)
+__device__ inline G1 g1_from_bytes(const uint8_t* b, bool* ok) {
+    bool all_zero = true;
+    for (int i = 0; i < 96; ++i) all_zero = all_zero && b[i] == 0;
+    if (all_zero) return g1_identity();
+    const Fq xp = fq_limbs_from_bytes(b), yp = fq_limbs_from_bytes(b + 48);
+    const Fq q = fq_const(fqc::Q);
+    if (!limbs_less(xp, q) || !limbs_less(yp, q)) *ok = false;
+    G1 p;
+    p.X = fq_to_mont(xp);
+    p.Y = fq_to_mont(yp);
+    p.Z = fq_one();
+    Fq four = fq_add(fq_one(), fq_one());
+    four = fq_add(four, four);
+    const Fq rhs = fq_add(fq_mul_ni(fq_mul_ni(p.X, p.X), p.X), four);
+    if (!fq_eq(fq_mul_ni(p.Y, p.Y), rhs)) *ok = false;
+    return p;
+}
+
+// One lane per term of two sums in one launch: the blocks below nb_bytes take the points given as affine bytes
+// (term t = 64 block + lane < n_bytes, scalar scal[t]), the others the key's generators (term t' = 64 (block -
+// nb_bytes) + lane < n_g1, scalar scal[n_bytes + t']).  Scalars: 8 words, canonical, little-endian.  A lane first
+// builds the 15 multiples of its point, then runs over the 64 4-bit windows from the top: four doublings and one
+// addition of a table entry (none for a zero digit).  A shuffle tree adds the block's terms: part[block].
+// bad[0] is set if a point given as bytes is malformed.
+__global__ __launch_bounds__(64) void k_msm_terms(const uint8_t* pts_bytes, uint64_t n_bytes, unsigned nb_bytes,
+                                                  const G1* pts_g1, uint64_t n_g1, const uint32_t* scal, G1* part,
+                                                  uint32_t* bad) {
+    const bool from_bytes = blockIdx.x < nb_bytes;
+    const uint64_t t = from_bytes ? blockIdx.x * (uint64_t)64 + threadIdx.x : (blockIdx.x - nb_bytes) * (uint64_t)64 + threadIdx.x;
+    const bool live = t < (from_bytes ? n_bytes : n_g1);
+    G1 acc = g1_identity();
+    G1 tab[15];
+    uint32_t k[8];
+#pragma unroll
+    for (int w = 0; w < 8; ++w) k[w] = 0;
+    if (live) {
+        bool ok = true;
+        tab[0] = from_bytes ? g1_from_bytes(pts_bytes + 96 * t, &ok) : pts_g1[t];
+        if (!ok) bad[0] = 1;
+        const uint32_t* sp = scal + 8 * (from_bytes ? t : n_bytes + t);
+#pragma unroll
+        for (int w = 0; w < 8; ++w) k[w] = sp[w];
+    } else {
+        tab[0] = g1_identity();
+    }
+#pragma unroll 1
+    for (int d = 1; d < 15; ++d) tab[d] = g1_add_ni(tab[d - 1], tab[0]);
+#pragma unroll 1
+    for (int win = 63; win >= 0; --win) {
+#pragma unroll 1
+        for (int q = 0; q < 4; ++q) acc = g1_dbl_ni(acc);
+        const uint32_t dg = (k[win >> 3] >> (4 * (win & 7))) & 15u;
+        if (dg) acc = g1_add_ni(acc, tab[dg - 1]);
+    }
+#pragma unroll 1
+    for (int off = 32; off >= 1; off >>= 1) acc = g1_add_ni(acc, g1_shfl_down(acc, off));
+    if (threadIdx.x == 0) part[blockIdx.x] = acc;
+}
+
+// out = affine bytes of the sum of part[0 .. n): one wave
+__global__ __launch_bounds__(64) void k_msm_finish(const G1* part, uint64_t n, uint8_t* out) {
+    G1 acc = g1_identity();
+    for (uint64_t i = threadIdx.x; i < n; i += 64) acc = g1_add_ni(acc, part[i]);
+#pragma unroll 1
+    for (int off = 32; off >= 1; off >>= 1) acc = g1_add_ni(acc, g1_shfl_down(acc, off));
+    if (threadIdx.x == 0) g1_to_bytes(acc, out);
+}
+
 __global__ __launch_bounds__(64) void k_ck_export(const G1* gens, uint64_t first, uint64_t count, uint8_t* out) {
     const uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
     if (i >= count) return;
@@ -351,5 +425,124 @@ extern "C" int hyrax_commit(zkdl_ctx* ctx, const zkdl_commit_key* key, const zkd
     if (rc != ZKDL_OK) return rc;
     ZK_HIP(ctx, e);
     *ncommit = rows;
+    return ZKDL_OK;
+}
+
+// host: beta~(u, .) over 2^m entries (Montgomery form), u canonical bytes
+static bool host_beta_table(const zkdl_fr* u, int m, std::vector<Fr>& out) {
+    out.assign((size_t)1 << m, fr_zero());
+    out[0] = fr_one();
+    size_t size = 1;
+    for (int k = m - 1; k >= 0; --k) {   // coordinate 0 pairs with the most significant bit
+        Fr x;
+        memcpy(x.v, u[k].le, 32);
+        bool below = false;
+        for (int l = 7; l >= 0 && !below; --l) {
+            if (x.v[l] > frc::MOD[l]) return false;
+            below = x.v[l] < frc::MOD[l];
+        }
+        if (!below) return false;
+        const Fr uk = fr_to_mont(x);
+        for (size_t b = 0; b < size; ++b) {
+            const Fr hi = fr_mul(out[b], uk);
+            out[b + size] = hi;
+            out[b] = fr_sub(out[b], hi);
+        }
+        size *= 2;
+    }
+    return true;
+}
+
+static bool host_fr_from_bytes(const zkdl_fr& a, Fr* mont) {
+    Fr x;
+    memcpy(x.v, a.le, 32);
+    bool below = false;
+    for (int l = 7; l >= 0 && !below; --l) {
+        if (x.v[l] > frc::MOD[l]) return false;
+        below = x.v[l] < frc::MOD[l];
+    }
+    if (!below) return false;
+    *mont = fr_to_mont(x);
+    return true;
+}
+
+extern "C" int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uint8_t* commitments, size_t nrows,
+                            const zkdl_fr* point, size_t npoint, const zkdl_fr* T, const zkdl_fr* rho, const zkdl_fr* y,
+                            int* verdict, uint8_t* combined_out) {
+    if (!ctx || !key || !commitments || !T || !y || !verdict || (npoint && !point)) return ZKDL_EINVAL;
+    if (nrows == 0 || (nrows & (nrows - 1)) || nrows > ((size_t)1 << 16)) return ZKDL_EINVAL;
+    int lr = 0;
+    while (((size_t)1 << lr) < nrows) ++lr;
+    if ((int)npoint < lr || (int)npoint - lr > 15) return ZKDL_EINVAL;
+    const int lc = (int)npoint - lr;
+    const uint64_t cols = (uint64_t)1 << lc;
+    if (cols > key->ncols) return ZKDL_EINVAL;
+    *verdict = 1;
+    // the weights of the rows and <T, beta~(v_col, .)> on the host (at most 2^16 + 2^15 products)
+    std::vector<Fr> b_row, b_col;
+    if (!host_beta_table(point, lr, b_row) || !host_beta_table(point + lr, lc, b_col)) return ZKDL_OK;
+    Fr acc = fr_zero(), ym, rm = fr_zero();
+    std::vector<uint32_t> scal(8 * (nrows + cols + 1) + 16, 0u);   // the last words: the kernels' error flag, zero
+    for (uint64_t c = 0; c < cols; ++c) {
+        Fr t;
+        if (!host_fr_from_bytes(T[c], &t)) return ZKDL_OK;
+        acc = fr_add(acc, fr_mul(b_col[c], t));
+        memcpy(&scal[8 * (nrows + c)], T[c].le, 32);
+    }
+    if (!host_fr_from_bytes(*y, &ym) || (rho && !host_fr_from_bytes(*rho, &rm))) return ZKDL_OK;
+    for (size_t j = 0; j < nrows; ++j) {
+        const Fr plain = fr_from_mont(b_row[j]);
+        memcpy(&scal[8 * j], plain.v, 32);
+    }
+    if (rho) memcpy(&scal[8 * (nrows + cols)], rho->le, 32);
+    else memset(&scal[8 * (nrows + cols)], 0, 32);
+    ZK_HIP(ctx, hipSetDevice(ctx->device));
+    // sum 1: the row commitments with the weights beta~(v_row, .); sum 2: Commit(T; rho*) on the key's generators
+    const uint64_t n2 = cols + 1;
+    const unsigned g1 = (unsigned)((nrows + 63) / 64), g2 = (unsigned)((n2 + 63) / 64);
+    uint8_t* d_comm = (uint8_t*)zk_alloc(ctx, nrows * 96);
+    uint32_t* d_scal = (uint32_t*)zk_alloc(ctx, scal.size() * 4);
+    G1* d_part = (G1*)zk_alloc(ctx, sizeof(G1) * (g1 + g2));
+    G1* d_gens = (G1*)zk_alloc(ctx, sizeof(G1) * n2);   // G_0 .. G_{cols-1}, H
+    uint8_t* d_out = (uint8_t*)zk_alloc(ctx, 256);
+    int rc = (d_comm && d_scal && d_part && d_gens && d_out) ? ZKDL_OK : ZKDL_ENOMEM;
+    uint8_t h_out[256];
+    hipError_t e = hipSuccess;
+    if (rc == ZKDL_OK) {
+        e = hipMemcpyAsync(d_comm, commitments, nrows * 96, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(d_scal, scal.data(), scal.size() * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(d_gens, key->gens, sizeof(G1) * cols, hipMemcpyDeviceToDevice, ctx->stream);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(d_gens + cols, key->gens + key->ncols, sizeof(G1), hipMemcpyDeviceToDevice, ctx->stream);
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(k_msm_terms, dim3(g1 + g2), dim3(64), 0, ctx->stream, d_comm, (uint64_t)nrows, g1, d_gens, n2,
+                               d_scal, d_part, d_scal + 8 * (nrows + cols + 1));
+            hipLaunchKernelGGL(k_msm_finish, dim3(1), dim3(64), 0, ctx->stream, d_part, (uint64_t)g1, d_out);
+            hipLaunchKernelGGL(k_msm_finish, dim3(1), dim3(64), 0, ctx->stream, d_part + g1, (uint64_t)g2, d_out + 96);
+            e = hipMemcpyAsync(h_out, d_out, 192, hipMemcpyDeviceToHost, ctx->stream);
+            if (e == hipSuccess)
+                e = hipMemcpyAsync(h_out + 192, d_scal + 8 * (nrows + cols + 1), 4, hipMemcpyDeviceToHost, ctx->stream);
+        }
+    }
+    hipError_t e2 = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess) e = e2;
+    if (e == hipSuccess) e = hipGetLastError();
+    zk_free(ctx, d_comm);
+    zk_free(ctx, d_scal);
+    zk_free(ctx, d_part);
+    zk_free(ctx, d_gens);
+    zk_free(ctx, d_out);
+    if (rc != ZKDL_OK) return rc;
+    ZK_HIP(ctx, e);
+    uint32_t bad;
+    memcpy(&bad, h_out + 192, 4);
+    if (bad) return ZKDL_OK;                       // verdict 1: a commitment is not a point of the curve
+    if (combined_out) memcpy(combined_out, h_out, 96);
+    if (memcmp(h_out, h_out + 96, 96) != 0) {
+        *verdict = 2;                              // Commit(T; rho*) is not the combined commitment
+        return ZKDL_OK;
+    }
+    *verdict = fr_eq(acc, ym) ? 0 : 3;             // 3: <T, beta~(v_col, .)> != y
     return ZKDL_OK;
 }

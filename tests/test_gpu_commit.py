@@ -67,6 +67,84 @@ def test_opening_is_accepted_by_the_oracles_verifier(lib, ctx):
     assert EC.verify_opening(coms, point, t, rho_star, y, gens, h)
 
 
+def _combined(coms, point, rows):
+    lr = rows.bit_length() - 1
+    from oracle.mle import beta_table
+    b = beta_table(point[:lr])
+    acc = EC.INF
+    for j in range(rows):
+        acc = EC.add(acc, EC.mul(int(b[j]), coms[j]))
+    return acc
+
+
+@pytest.mark.parametrize("numel,dtype,blinded", [(1, "i32", True), (2, "i32", True), (128, "i32", True), (256, "i64", False),
+                                                 (2048, "i32", True)])
+def test_library_verifies_openings_as_the_oracle_does(lib, ctx, numel, dtype, blinded):
+    """hyrax_verify: the combined commitment equals the oracle's byte for byte; the library's opening is accepted;
+    a changed row entry, blinding, value, commitment or point is refused with the verdict of the check that the
+    oracle's verifier fails at."""
+    import torch
+    say(f"hyrax_verify numel={numel} {dtype} blinded={blinded}")
+    rng = np.random.default_rng(numel + 11)
+    if dtype == "i32":
+        vals = rng.integers(-2 ** 31, 2 ** 31, numel, dtype=np.int64).astype(np.int32)
+    else:
+        vals = rng.integers(-2 ** 60, 2 ** 60, numel, dtype=np.int64)
+    rows, cols = EC.matrix_shape(numel)
+    key = lib.CommitKey(ctx, b"vfy", cols, 64 if dtype == "i64" else 32)
+    blind = [int.from_bytes(rng.bytes(31), "little") for _ in range(rows)] if blinded else None
+    x = lib.tensor_wrap_int(ctx, torch.from_numpy(vals).cuda())
+    raw = lib.hyrax_commit(ctx, key, x, blind)
+    m = numel.bit_length() - 1
+    point = [int.from_bytes(rng.bytes(31), "little") for _ in range(m)]
+    t, rho_star, y = lib.hyrax_open(ctx, x, blind, point)
+    verdict, comb = lib.hyrax_verify(ctx, key, raw, point, t, rho_star if blinded else None, y)
+    coms = [EC.point_from_bytes(c) for c in raw]
+    assert comb == EC.point_to_bytes(_combined(coms, point, rows))
+    assert verdict == 0
+    gens, h = EC.generators(b"vfy", cols)
+    assert EC.verify_opening(coms, point, t, rho_star if blinded else 0, y, gens, h)
+    # tampering, with the oracle's verifier beside it
+    def both(raw_, point_, t_, rho_, y_, want):
+        v, _ = lib.hyrax_verify(ctx, key, raw_, point_, t_, rho_, y_)
+        assert v == want
+        with pytest.raises(AssertionError):
+            EC.verify_opening([EC.point_from_bytes(c) for c in raw_], point_, t_, rho_ or 0, y_, gens, h)
+    rho_in = rho_star if blinded else None
+    both(raw, point, t, rho_in, (y + 1) % R_MOD, 3)
+    both(raw, point, [(t[0] + 1) % R_MOD] + t[1:], rho_in, y, 2)
+    if blinded:
+        both(raw, point, t, (rho_star + 1) % R_MOD, y, 2)
+    if rows > 1:
+        both([raw[1], raw[0]] + raw[2:], point, t, rho_in, y, 2)
+        both(raw, [(point[0] + 1) % R_MOD] + point[1:], t, rho_in, y, 2)
+    # malformed inputs: a commitment off the curve, an element not below r
+    off = bytearray(raw[0])
+    off[0] ^= 1
+    assert lib.hyrax_verify(ctx, key, [bytes(off)] + raw[1:], point, t, rho_in, y)[0] == 1
+    assert lib.hyrax_verify(ctx, key, raw, point, [R_MOD] + t[1:], rho_in, y)[0] == 1
+
+
+def test_library_verifies_the_full_size_opening(lib, ctx):
+    """The 2^19 activation stack: 1024 row commitments combined and the 512-entry row recommitted on the GPU."""
+    import torch
+    from workloads import fcnn_window, CONFIG_SEED
+    say("hyrax_verify on the 2^19 activation stack")
+    wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)
+    vals = np.ascontiguousarray(wit["A"]).reshape(-1)
+    rows, cols = EC.matrix_shape(vals.size)
+    rng = np.random.default_rng(12)
+    blind = [int.from_bytes(rng.bytes(31), "little") for _ in range(rows)]
+    key = lib.CommitKey(ctx, b"A", cols)
+    x = lib.tensor_wrap_int(ctx, torch.from_numpy(vals).cuda())
+    raw = lib.hyrax_commit(ctx, key, x, blind)
+    point = [int.from_bytes(rng.bytes(31), "little") for _ in range(19)]
+    t, rho_star, y = lib.hyrax_open(ctx, x, blind, point)
+    assert lib.hyrax_verify(ctx, key, raw, point, t, rho_star, y)[0] == 0
+    assert lib.hyrax_verify(ctx, key, raw, point, t, rho_star, (y + 1) % R_MOD)[0] == 3
+    assert lib.hyrax_verify(ctx, key, raw[1:] + raw[:1], point, t, rho_star, y)[0] == 2
+
+
 def test_commitments_are_homomorphic(lib, ctx):
     """Sec. 2.3: the product of two commitments commits to the sum of the tensors."""
     import torch
