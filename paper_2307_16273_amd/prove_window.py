@@ -91,8 +91,18 @@ def main():
             zk.hyrax_commit(ctx, key, xv)
             t0 = time.perf_counter()
             cm = zk.hyrax_commit(ctx, key, xv)
-            print(json.dumps({"commit": nm, "entries": int(flat.numel()), "rows": len(cm),
-                              "commit_ms": 1e3 * (time.perf_counter() - t0)}), flush=True)
+            line = {"commit": nm, "entries": int(flat.numel()), "rows": len(cm), "commit_ms": 1e3 * (time.perf_counter() - t0)}
+            if args.form == "linked" and res is not None:
+                # the one claim the chained window leaves on this stack, opened against the commitment and checked
+                claim = {c["tensor"]: c for c in res["claims_left"]}[nm]
+                t0 = time.perf_counter()
+                t_row, _, y = zk.hyrax_open(ctx, xv, None, claim["point"])
+                line["open_ms"] = 1e3 * (time.perf_counter() - t0)
+                t0 = time.perf_counter()
+                verdict, _ = zk.hyrax_verify(ctx, key, cm, claim["point"], t_row, None, claim["value"])
+                line["open_verify_ms"] = 1e3 * (time.perf_counter() - t0)
+                line["claim_opens"] = bool(y == claim["value"] and verdict == 0)
+            print(json.dumps(line), flush=True)
             key.close()
     ctx.close()
 

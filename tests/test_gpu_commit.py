@@ -145,6 +145,39 @@ def test_library_verifies_the_full_size_opening(lib, ctx):
     assert lib.hyrax_verify(ctx, key, raw[1:] + raw[:1], point, t, rho_star, y)[0] == 2
 
 
+def test_claims_of_a_chained_window_open_against_the_commitments(lib, ctx):
+    """Protocol zkdl end to end on one small window: the stacks A and W are committed, the chained window is
+    proved, and the one claim it leaves on each of them is what the commitment opens to at the claim's point
+    (proof of evaluation made and verified by the library, and by the oracle's verifier)."""
+    import torch
+    from workloads import fcnn_window, CONFIG_SEED
+    say("commit -> prove -> open -> verify on a window")
+    wit = fcnn_window(CONFIG_SEED + 140, n_layers=2, width=8, batch=4, steps=2)
+    dw = {k: wit[k] for k in ("L", "B", "width", "T", "Q", "R")}
+    for k in ("A", "W", "GZ", "Zr", "GA"):
+        dw[k] = torch.from_numpy(np.ascontiguousarray(wit[k])).cuda()
+    rng = np.random.default_rng(21)
+    committed = {}
+    for nm in ("A", "W"):
+        flat = dw[nm].reshape(-1)
+        rows, cols = EC.matrix_shape(flat.numel())
+        key = lib.CommitKey(ctx, nm.encode(), cols)
+        blind = [int.from_bytes(rng.bytes(31), "little") for _ in range(rows)]
+        x = lib.tensor_wrap_int(ctx, flat)
+        committed[nm] = (key, x, blind, lib.hyrax_commit(ctx, key, x, blind), cols)
+    got = lib.aggregate_prove(ctx, dw, lib.Transcript(77), linked=True)
+    left = {c["tensor"]: c for c in got["claims_left"]}
+    for nm in ("A", "W"):
+        key, x, blind, coms, cols = committed[nm]
+        claim = left[nm]
+        t, rho_star, y = lib.hyrax_open(ctx, x, blind, claim["point"])
+        assert y == claim["value"]
+        assert lib.hyrax_verify(ctx, key, coms, claim["point"], t, rho_star, claim["value"])[0] == 0
+        gens, h = EC.generators(nm.encode(), cols)
+        assert EC.verify_opening([EC.point_from_bytes(c) for c in coms], claim["point"], t, rho_star, claim["value"], gens, h)
+        assert lib.hyrax_verify(ctx, key, coms, claim["point"], t, rho_star, (claim["value"] + 1) % R_MOD)[0] == 3
+
+
 def test_commitments_are_homomorphic(lib, ctx):
     """Sec. 2.3: the product of two commitments commits to the sum of the tensors."""
     import torch
