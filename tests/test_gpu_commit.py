@@ -5,6 +5,7 @@ import pytest
 
 from oracle import curve as EC
 from oracle.field import R_MOD
+from oracle.transcript import Transcript as OracleTranscript
 
 pytestmark = pytest.mark.gpu
 
@@ -165,7 +166,16 @@ def test_claims_of_a_chained_window_open_against_the_commitments(lib, ctx):
         blind = [int.from_bytes(rng.bytes(31), "little") for _ in range(rows)]
         x = lib.tensor_wrap_int(ctx, flat)
         committed[nm] = (key, x, blind, lib.hyrax_commit(ctx, key, x, blind), cols)
-    got = lib.aggregate_prove(ctx, dw, lib.Transcript(77), linked=True)
+    # the commitments go into the transcript before anything is drawn (Protocol zkdl: the prover commits first)
+    tr = lib.Transcript(77)
+    ots = OracleTranscript(77)
+    for nm in ("A", "W"):
+        tr.absorb(b"commit", b"".join(committed[nm][3]))
+        ots.absorb(b"commit", b"".join(committed[nm][3]))
+    got = lib.aggregate_prove(ctx, dw, tr, linked=True)
+    from oracle import protocols as P
+    P.aggregate_linked_verify(got["proof"], ots)             # the oracle's verifier on the same bound transcript
+    assert ots.digest() == tr.digest()
     left = {c["tensor"]: c for c in got["claims_left"]}
     for nm in ("A", "W"):
         key, x, blind, coms, cols = committed[nm]
