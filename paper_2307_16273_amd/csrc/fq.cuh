@@ -169,6 +169,119 @@ FQ_HD Fq fq_pow(const Fq& a, const uint32_t (&e)[WORDS]) {
 
 FQ_HD Fq fq_inv(const Fq& a) { return fq_pow(a, fqc::EXP_INV); }
 
+// ---- inversion by the binary Euclidean algorithm ---------------------------------------------------------------
+// u = a, v = q (odd throughout).  One trip: if u is odd, the smaller of u, v is taken from the larger (u becomes the
+// difference, v the smaller one); then u is halved.  Instead of halving a cofactor modulo q the other one is doubled
+// (Kaliski's almost-inverse): with S, R >= 0 and a sign, a (sign S) = u 2^k and a (sign R) = -v 2^k modulo q after k
+// halvings, and S v + R u = q bounds both by q.  At u = 0, v = 1: 1/a = -sign R / 2^k, with 381 <= k <= 762.
+// About 270 trips of a few 12-word operations instead of the ~570 field products of a^(q-2).  The running time
+// depends on the value: for public data only (commitments, the verifier).
+namespace fqe {
+constexpr int W = 12;
+struct U384 {
+    uint32_t w[W];
+};
+
+FQ_HD U384 from_limbs(const Fq& a) {   // normal limbs, value below 2^384
+    U384 o;
+#pragma unroll
+    for (int j = 0; j < W; ++j) {
+        uint64_t x = 0;
+#pragma unroll
+        for (int i = 0; i < fqc::L; ++i) {
+            const int sh = 29 * i - 32 * j;   // limb i covers bits [29 i, 29 i + 29)
+            if (sh > -29 && sh < 32) x |= sh >= 0 ? ((uint64_t)a.v[i] << sh) : ((uint64_t)a.v[i] >> (-sh));
+        }
+        o.w[j] = (uint32_t)x;
+    }
+    return o;
+}
+
+FQ_HD Fq to_limbs(const U384& a) {
+    Fq o;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        const int bit = 29 * i, j = bit >> 5, sh = bit & 31;
+        uint64_t x = a.w[j];
+        if (j + 1 < W) x |= (uint64_t)a.w[j + 1] << 32;
+        o.v[i] = (uint32_t)(x >> sh) & fqc::M29;
+    }
+    return o;
+}
+}  // namespace fqe
+
+// 1/a in Montgomery form for a in Montgomery form (0 for 0)
+FQ_HD Fq fq_inv_euclid(const Fq& a) {
+    using fqe::U384;
+    using fqe::W;
+    U384 u = fqe::from_limbs(a), v = fqe::from_limbs(fq_const(fqc::Q)), S, R;
+#pragma unroll
+    for (int i = 0; i < W; ++i) S.w[i] = R.w[i] = 0;
+    S.w[0] = 1;
+    uint32_t flip = 0;
+    int k = 0;
+    for (;;) {
+        const uint32_t odd = 0u - (u.w[0] & 1u);
+        U384 d;
+        uint32_t bor = 0;
+#pragma unroll
+        for (int i = 0; i < W; ++i) {   // d = u - v modulo 2^384
+            const uint64_t x = (uint64_t)u.w[i] - v.w[i] - bor;
+            d.w[i] = (uint32_t)x;
+            bor = (uint32_t)(x >> 63);
+        }
+        const uint32_t sw = odd & (0u - bor);   // u odd and below v: the roles change
+        uint32_t c = sw & 1u;
+#pragma unroll
+        for (int i = 0; i < W; ++i) {   // |u - v|
+            const uint64_t x = (uint64_t)(d.w[i] ^ sw) + c;
+            d.w[i] = (uint32_t)x;
+            c = (uint32_t)(x >> 32);
+        }
+        c = 0;
+        uint32_t any = 0;
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            v.w[i] = sw ? u.w[i] : v.w[i];
+            u.w[i] = odd ? d.w[i] : u.w[i];
+            any |= u.w[i];
+            const uint32_t s_old = S.w[i], r_old = R.w[i];
+            const uint32_t s_new = sw ? r_old : s_old, r_new = sw ? s_old : r_old;
+            const uint64_t x = (uint64_t)s_new + (r_new & odd) + c;   // S += R when u was odd
+            S.w[i] = (uint32_t)x;
+            c = (uint32_t)(x >> 32);
+            R.w[i] = r_new;
+        }
+        flip ^= sw & 1u;
+        if (any == 0) break;   // v = 1 now; R is not doubled any more (R u <= q bounds it only while u > 0)
+        // u is even here (it was, or it is a difference of two odd numbers): all its low zero bits at once, at most 31
+        const int tz = __builtin_ctz(u.w[0] | 0x80000000u);
+#pragma unroll
+        for (int i = 0; i < W; ++i) u.w[i] = (u.w[i] >> tz) | (i + 1 < W ? u.w[i + 1] << (32 - tz) : 0u);
+#pragma unroll
+        for (int i = W - 1; i >= 0; --i) R.w[i] = (R.w[i] << tz) | (i ? R.w[i - 1] >> (32 - tz) : 0u);
+        k += tz;
+    }
+    // the limbs of a hold a_true 2^406, so 1/limbs = (1/a_true) 2^-406 = -sign R 2^-k, and the Montgomery form of
+    // 1/a_true is -sign R 2^(812 - k): two products by single bits 2^e1 2^e2 = 2^(812 - k) (each takes 2^406 away)
+    // and two by 2^812 (each puts 2^406 back)
+    int e = 812 - k;
+    if (e < 0) e = 0;   // not reached: k <= 762
+    if (e > 810) e = 810;   // not reached for a != 0: k >= 381
+    const int e1 = e < 405 ? e : 405, e2 = e - e1;
+    Fq b1 = fq_zero(), b2 = fq_zero();
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        b1.v[i] = (e1 / 29 == i) ? (1u << (e1 % 29)) : 0u;
+        b2.v[i] = (e2 / 29 == i) ? (1u << (e2 % 29)) : 0u;
+    }
+    const Fq r2 = fq_const(fqc::R2);
+    Fq y = fq_mul(fqe::to_limbs(R), b1);   // R <= q as the first operand
+    y = fq_mul(y, b2);
+    y = fq_mul(fq_mul(y, r2), r2);
+    return flip ? y : fq_neg(y);
+}
+
 // 48 little-endian bytes (any value below 2^384) -> normal limbs of the plain value
 FQ_HD Fq fq_limbs_from_bytes(const uint8_t* p) {
     Fq o;
@@ -319,7 +432,7 @@ FQ_HD void g1_to_bytes(const G1& p, uint8_t* out) {
         for (int b = 0; b < 96; ++b) out[b] = 0;
         return;
     }
-    const Fq zi = fq_inv(p.Z);
+    const Fq zi = fq_inv_euclid(p.Z);
     fq_limbs_to_bytes(fq_from_mont(fq_mul(p.X, zi)), out);
     fq_limbs_to_bytes(fq_from_mont(fq_mul(p.Y, zi)), out + 48);
 }

@@ -205,8 +205,6 @@ __global__ __launch_bounds__(64) void k_commit_affine(const G1* sums, uint64_t r
 }
 
 // ---- the verifier's side of an opening: two sums of scalar multiples with full field elements as scalars ----
-__device__ inline G1 g1_dbl_ni(const G1& p) { return g1_dbl_with(p, FqMulOutOfLine()); }
-
 // 96 affine bytes -> Montgomery projective; *ok = false unless both coordinates are below q and the point is on
 // the curve (or the bytes are all zero: the identity)
 __device__ inline G1 g1_from_bytes(const uint8_t* b, bool* ok) {
@@ -227,54 +225,196 @@ __device__ inline G1 g1_from_bytes(const uint8_t* b, bool* ok) {
     return p;
 }
 
-// One lane per term of two sums in one launch: the blocks below nb_bytes take the points given as affine bytes
-// (term t = 64 block + lane < n_bytes, scalar scal[t]), the others the key's generators (term t' = 64 (block -
-// nb_bytes) + lane < n_g1, scalar scal[n_bytes + t']).  Scalars: 8 words, canonical, little-endian.  A lane first
-// builds the 15 multiples of its point, then runs over the 64 4-bit windows from the top: four doublings and one
-// addition of a table entry (none for a zero digit).  A shuffle tree adds the block's terms: part[block].
+// ---- a point operation shared by eight lanes -----------------------------------------------------------------
+// The complete addition and doubling are two levels of six (four) independent field products with linear steps
+// between them.  A group of eight lanes holds the same operands; lane j of the group takes the j-th product of each
+// level, the products go round the group by shuffles, and the linear steps are integer combinations of them with
+// small coefficients, shifted by a multiple of q so that they stay non-negative, with one carry pass and no
+// reduction: the Montgomery product accepts operands up to 2^12 q as long as the limbs are normal.  Coordinates stay
+// below 2q between operations (normal limbs); `g1_canonical` reduces them at the end.  An operation is about two
+// dependent field products long instead of twelve (eight).
+constexpr int COOP = 8;   // lanes per point
+
+// level 1: which coordinates of the first / second operand lane j adds up (bit 0 X, bit 1 Y, bit 2 Z)
+__device__ const uint8_t COOP_PICK[2][2][COOP] = {
+    {{1, 2, 4, 3, 6, 5, 0, 0}, {1, 2, 4, 3, 6, 5, 0, 0}},    // addition: X1X2, Y1Y2, Z1Z2, (X1+Y1)(X2+Y2), (Y1+Z1)(Y2+Z2), (X1+Z1)(X2+Z2)
+    {{2, 2, 4, 1, 0, 0, 0, 0}, {2, 4, 4, 2, 0, 0, 0, 0}}};   // doubling: Y Y, Y Z, Z Z, X Y
+// level 2: the two operands of lane j as combinations of the six level-1 products, last entry: multiples of q
+//   addition (T = t0, t1, t2, p3, p4, p5):  t3 = p3 - t0 - t1, t4 = p4 - t1 - t2, y3 = 12 (p5 - t0 - t2),
+//     t1' = t1 - 12 t2, z3 = t1 + 12 t2, x3 = 3 t0;  products t4 y3, t3 t1', y3 x3, t1' z3, x3 t3, z3 t4
+//   doubling (T = Y^2, YZ, Z^2, XY):  products (12 Z^2)(8 Y^2), (YZ)(8 Y^2), (Y^2 - 36 Z^2)(Y^2 + 12 Z^2), (Y^2 - 36 Z^2)(XY)
+__device__ const int8_t COOP_LIN[2][COOP][2][7] = {
+    {{{0, -1, -1, 0, 1, 0, 2}, {-12, 0, -12, 0, 0, 12, 24}},
+     {{-1, -1, 0, 1, 0, 0, 2}, {0, 1, -12, 0, 0, 0, 12}},
+     {{-12, 0, -12, 0, 0, 12, 24}, {3, 0, 0, 0, 0, 0, 0}},
+     {{0, 1, -12, 0, 0, 0, 12}, {0, 1, 12, 0, 0, 0, 0}},
+     {{3, 0, 0, 0, 0, 0, 0}, {-1, -1, 0, 1, 0, 0, 2}},
+     {{0, 1, 12, 0, 0, 0, 0}, {0, -1, -1, 0, 1, 0, 2}},
+     {{0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0}},
+     {{0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0}}},
+    {{{0, 0, 12, 0, 0, 0, 0}, {8, 0, 0, 0, 0, 0, 0}},
+     {{0, 1, 0, 0, 0, 0, 0}, {8, 0, 0, 0, 0, 0, 0}},
+     {{1, 0, -36, 0, 0, 0, 36}, {1, 0, 12, 0, 0, 0, 0}},
+     {{1, 0, -36, 0, 0, 0, 36}, {0, 0, 0, 1, 0, 0, 0}},
+     {{0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0}},
+     {{0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0}},
+     {{0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0}},
+     {{0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0}}}};
+
+__device__ inline Fq coop_pick(const G1& p, uint32_t sel) {
+    const uint32_t mx = 0u - (sel & 1u), my = 0u - ((sel >> 1) & 1u), mz = 0u - ((sel >> 2) & 1u);
+    Fq o;
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        const uint32_t x = (p.X.v[i] & mx) + (p.Y.v[i] & my) + (p.Z.v[i] & mz) + c;
+        o.v[i] = i < fqc::L - 1 ? (x & fqc::M29) : x;
+        c = i < fqc::L - 1 ? (x >> 29) : 0;
+    }
+    return o;
+}
+
+// sum_s c[s] T[s] + c[6] q, carried into normal limbs (the caller's coefficients keep it in [0, 2^12 q))
+__device__ inline Fq coop_lin(const Fq (&T)[6], const int (&c)[7]) {
+    Fq o;
+    int64_t acc = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        acc += (int64_t)c[6] * (int64_t)fqc::Q[i];
+#pragma unroll
+        for (int s = 0; s < 6; ++s) acc += (int64_t)c[s] * (int64_t)T[s].v[i];
+        o.v[i] = i < fqc::L - 1 ? ((uint32_t)acc & fqc::M29) : (uint32_t)acc;
+        acc >>= 29;
+    }
+    return o;
+}
+
+__device__ inline void coop_gather(const Fq& mine, Fq (&T)[6]) {
+#pragma unroll
+    for (int s = 0; s < 6; ++s)
+#pragma unroll
+        for (int i = 0; i < fqc::L; ++i) T[s].v[i] = __shfl(mine.v[i], s, COOP);
+}
+
+// MODE 0: p + q, MODE 1: 2 p (q is not read).  Every lane of the group passes the same operands and gets the same
+// result; all 64 lanes of the wave must call it together.
+template <int MODE>
+__device__ inline G1 g1_coop(const G1& p, const G1& q, int j) {
+    Fq T[6];
+    coop_gather(fq_mul_ni(coop_pick(p, COOP_PICK[MODE][0][j]), coop_pick(MODE ? p : q, COOP_PICK[MODE][1][j])), T);
+    int ca[7], cb[7];
+#pragma unroll
+    for (int s = 0; s < 7; ++s) {
+        ca[s] = COOP_LIN[MODE][j][0][s];
+        cb[s] = COOP_LIN[MODE][j][1][s];
+    }
+    coop_gather(fq_mul_ni(coop_lin(T, ca), coop_lin(T, cb)), T);
+    G1 r;
+    if (MODE == 0) {
+        const int cx[7] = {-1, 1, 0, 0, 0, 0, 1}, cy[7] = {0, 0, 1, 1, 0, 0, 0}, cz[7] = {0, 0, 0, 0, 1, 1, 0};
+        r.X = coop_lin(T, cx);
+        r.Y = coop_lin(T, cy);
+        r.Z = coop_lin(T, cz);
+    } else {
+        const int cx[7] = {0, 0, 0, 2, 0, 0, 0}, cy[7] = {1, 0, 1, 0, 0, 0, 0};
+        r.X = coop_lin(T, cx);
+        r.Y = coop_lin(T, cy);
+        r.Z = T[1];
+    }
+    return r;
+}
+
+__device__ inline G1 g1_canonical(const G1& p) {   // coordinates below 2q -> below q
+    G1 r;
+    r.X = fq_cond_sub(p.X);
+    r.Y = fq_cond_sub(p.Y);
+    r.Z = fq_cond_sub(p.Z);
+    return r;
+}
+
+constexpr int MSM_TERMS = 64 / COOP;   // terms per block
+constexpr int G1_WORDS = 3 * fqc::L;
+
+// Eight lanes per term of two sums in one launch: the blocks below nb_bytes take the points given as affine bytes
+// (term t = 8 block + group < n_bytes, scalar scal[t]), the others the key's generators (term t' = 8 (block -
+// nb_bytes) + group < n_g1, scalar scal[n_bytes + t']).  Scalars: 8 words, canonical, little-endian.  A group first
+// builds the 15 multiples of its point (in LDS), then runs over the 64 4-bit windows from the top: four doublings
+// and one addition of a table entry (of the identity for a zero digit: the formulas are complete, and the wave
+// stays in step).  Three more additions sum the block's terms: part[block], coordinates below 2q.
 // bad[0] is set if a point given as bytes is malformed.
 __global__ __launch_bounds__(64) void k_msm_terms(const uint8_t* pts_bytes, uint64_t n_bytes, unsigned nb_bytes,
                                                   const G1* pts_g1, uint64_t n_g1, const uint32_t* scal, G1* part,
                                                   uint32_t* bad) {
+    __shared__ uint32_t tab[MSM_TERMS][15][G1_WORDS];
+    const int j = threadIdx.x % COOP, grp = threadIdx.x / COOP;
     const bool from_bytes = blockIdx.x < nb_bytes;
-    const uint64_t t = from_bytes ? blockIdx.x * (uint64_t)64 + threadIdx.x : (blockIdx.x - nb_bytes) * (uint64_t)64 + threadIdx.x;
+    const uint64_t t = (from_bytes ? blockIdx.x : blockIdx.x - nb_bytes) * (uint64_t)MSM_TERMS + grp;
     const bool live = t < (from_bytes ? n_bytes : n_g1);
-    G1 acc = g1_identity();
-    G1 tab[15];
+    G1 base = g1_identity();
     uint32_t k[8];
 #pragma unroll
     for (int w = 0; w < 8; ++w) k[w] = 0;
     if (live) {
         bool ok = true;
-        tab[0] = from_bytes ? g1_from_bytes(pts_bytes + 96 * t, &ok) : pts_g1[t];
+        base = from_bytes ? g1_from_bytes(pts_bytes + 96 * t, &ok) : pts_g1[t];
         if (!ok) bad[0] = 1;
         const uint32_t* sp = scal + 8 * (from_bytes ? t : n_bytes + t);
 #pragma unroll
         for (int w = 0; w < 8; ++w) k[w] = sp[w];
-    } else {
-        tab[0] = g1_identity();
     }
+    G1 acc = base;
 #pragma unroll 1
-    for (int d = 1; d < 15; ++d) tab[d] = g1_add_ni(tab[d - 1], tab[0]);
+    for (int d = 0; d < 15; ++d) {   // tab[d] = (d + 1) base
+        if (d) acc = g1_coop<0>(acc, base, j);
+        if (j == 0) {
+#pragma unroll
+            for (int i = 0; i < fqc::L; ++i) {
+                tab[grp][d][i] = acc.X.v[i];
+                tab[grp][d][fqc::L + i] = acc.Y.v[i];
+                tab[grp][d][2 * fqc::L + i] = acc.Z.v[i];
+            }
+        }
+    }
+    __syncthreads();
+    acc = g1_identity();
 #pragma unroll 1
     for (int win = 63; win >= 0; --win) {
 #pragma unroll 1
-        for (int q = 0; q < 4; ++q) acc = g1_dbl_ni(acc);
+        for (int q = 0; q < 4; ++q) acc = g1_coop<1>(acc, acc, j);
         const uint32_t dg = (k[win >> 3] >> (4 * (win & 7))) & 15u;
-        if (dg) acc = g1_add_ni(acc, tab[dg - 1]);
+        G1 e = g1_identity();
+        if (dg) {
+            const uint32_t* src = tab[grp][dg - 1];
+#pragma unroll
+            for (int i = 0; i < fqc::L; ++i) {
+                e.X.v[i] = src[i];
+                e.Y.v[i] = src[fqc::L + i];
+                e.Z.v[i] = src[2 * fqc::L + i];
+            }
+        }
+        acc = g1_coop<0>(acc, e, j);
     }
 #pragma unroll 1
-    for (int off = 32; off >= 1; off >>= 1) acc = g1_add_ni(acc, g1_shfl_down(acc, off));
+    for (int off = 32; off >= COOP; off >>= 1) acc = g1_coop<0>(acc, g1_shfl_down(acc, off), j);
     if (threadIdx.x == 0) part[blockIdx.x] = acc;
 }
 
-// out = affine bytes of the sum of part[0 .. n): one wave
-__global__ __launch_bounds__(64) void k_msm_finish(const G1* part, uint64_t n, uint8_t* out) {
+// Block b: out + 96 b = affine bytes of the sum of part[first[b] .. first[b] + count[b]) (coordinates below 2q): one
+// wave, eight groups of lanes adding every eighth partial sum, three more additions, one inversion.
+__global__ __launch_bounds__(64) void k_msm_finish(const G1* part, uint64_t n0, uint64_t n1, uint8_t* out) {
+    const int j = threadIdx.x % COOP, grp = threadIdx.x / COOP;
+    const G1* src = blockIdx.x ? part + n0 : part;
+    const uint64_t n = blockIdx.x ? n1 : n0;
     G1 acc = g1_identity();
-    for (uint64_t i = threadIdx.x; i < n; i += 64) acc = g1_add_ni(acc, part[i]);
 #pragma unroll 1
-    for (int off = 32; off >= 1; off >>= 1) acc = g1_add_ni(acc, g1_shfl_down(acc, off));
-    if (threadIdx.x == 0) g1_to_bytes(acc, out);
+    for (uint64_t i = 0; i < n; i += MSM_TERMS) {   // every group runs the same number of trips
+        const uint64_t at = i + grp;
+        const G1 e = at < n ? src[at] : g1_identity();
+        acc = g1_coop<0>(acc, e, j);
+    }
+#pragma unroll 1
+    for (int off = 32; off >= COOP; off >>= 1) acc = g1_coop<0>(acc, g1_shfl_down(acc, off), j);
+    if (threadIdx.x == 0) g1_to_bytes(g1_canonical(acc), out + 96 * blockIdx.x);
 }
 
 __global__ __launch_bounds__(64) void k_ck_export(const G1* gens, uint64_t first, uint64_t count, uint8_t* out) {
@@ -308,6 +448,20 @@ extern "C" int zkdl_commit_selfcheck(void) {
     if (!fq_eq(fq_mul(fq_inv(three), three), fq_one())) return ZKDL_EINVAL;
     Fq root = fq_pow(fq_sqr(three), fqc::EXP_SQRT);
     if (!fq_eq(root, three) && !fq_eq(root, fq_neg(three))) return ZKDL_EINVAL;
+    // the Euclidean inversion against a^(q-2): limb values 1, 2, q - 1, 2^380, then a chain of products
+    Fq probe[16];
+    probe[0] = fq_zero();
+    probe[0].v[0] = 1;
+    probe[1] = fq_add(probe[0], probe[0]);
+    probe[2] = fq_sub(fq_zero(), probe[0]);
+    probe[3] = fq_zero();
+    probe[3].v[13] = 1u << 3;
+    probe[4] = fq_one();
+    probe[5] = fq_neg(fq_one());
+    for (int i = 6; i < 16; ++i) probe[i] = fq_add(fq_mul(probe[i - 1], fq_add(three, probe[i - 3])), probe[i - 2]);
+    for (int i = 0; i < 16; ++i)
+        if (!fq_eq(fq_inv_euclid(probe[i]), fq_inv(probe[i]))) return ZKDL_EINVAL;
+    if (!fq_is_zero(fq_inv_euclid(fq_zero()))) return ZKDL_EINVAL;
     return ZKDL_OK;
 }
 
@@ -499,7 +653,7 @@ extern "C" int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uin
     ZK_HIP(ctx, hipSetDevice(ctx->device));
     // sum 1: the row commitments with the weights beta~(v_row, .); sum 2: Commit(T; rho*) on the key's generators
     const uint64_t n2 = cols + 1;
-    const unsigned g1 = (unsigned)((nrows + 63) / 64), g2 = (unsigned)((n2 + 63) / 64);
+    const unsigned g1 = (unsigned)((nrows + MSM_TERMS - 1) / MSM_TERMS), g2 = (unsigned)((n2 + MSM_TERMS - 1) / MSM_TERMS);
     uint8_t* d_comm = (uint8_t*)zk_alloc(ctx, nrows * 96);
     uint32_t* d_scal = (uint32_t*)zk_alloc(ctx, scal.size() * 4);
     G1* d_part = (G1*)zk_alloc(ctx, sizeof(G1) * (g1 + g2));
@@ -518,8 +672,7 @@ extern "C" int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uin
         if (e == hipSuccess) {
             hipLaunchKernelGGL(k_msm_terms, dim3(g1 + g2), dim3(64), 0, ctx->stream, d_comm, (uint64_t)nrows, g1, d_gens, n2,
                                d_scal, d_part, d_scal + 8 * (nrows + cols + 1));
-            hipLaunchKernelGGL(k_msm_finish, dim3(1), dim3(64), 0, ctx->stream, d_part, (uint64_t)g1, d_out);
-            hipLaunchKernelGGL(k_msm_finish, dim3(1), dim3(64), 0, ctx->stream, d_part + g1, (uint64_t)g2, d_out + 96);
+            hipLaunchKernelGGL(k_msm_finish, dim3(2), dim3(64), 0, ctx->stream, d_part, (uint64_t)g1, (uint64_t)g2, d_out);
             e = hipMemcpyAsync(h_out, d_out, 192, hipMemcpyDeviceToHost, ctx->stream);
             if (e == hipSuccess)
                 e = hipMemcpyAsync(h_out + 192, d_scal + 8 * (nrows + cols + 1), 4, hipMemcpyDeviceToHost, ctx->stream);
