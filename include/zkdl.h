@@ -515,8 +515,8 @@ int hyrax_open(zkdl_ctx* ctx, const zkdl_tensor* X, const zkdl_fr* blind, const 
  * + log2 C canonical elements, row coordinates first; T: C elements; rho: rho* or NULL for zero blinding.
  * *verdict = 0 accepted, 1 malformed input (an element not below r, a commitment not on the curve), 2 the opened
  * row does not match the combined commitment, 3 wrong evaluation.  combined_out (may be NULL): C* as 96 bytes.
- * Both sums run on the GPU, one lane per term (double-and-add over the 255-bit scalar), the weights and the
- * inner product on the host. */
+ * Both sums run on the GPU, eight lanes per term (4-bit windows over the 255-bit scalar, every point operation
+ * shared by the eight), the weights and the inner product on the host. */
 int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uint8_t* commitments, size_t nrows,
                  const zkdl_fr* point, size_t npoint, const zkdl_fr* T, const zkdl_fr* rho, const zkdl_fr* y,
                  int* verdict, uint8_t* combined_out);
