@@ -487,7 +487,8 @@ int zkdl_host_aggregate_verify(const uint8_t* proof, size_t proof_len, zkdl_tran
  * tag = "zkdl-mi355x/g1/" || label; the first x for which x^3 + 4 is a square gives (x, y) with the smaller
  * root y, multiplied by the cofactor (a candidate that becomes the identity is skipped); H is index
  * 0xFFFFFFFF.  ncols a power of two up to 2^15; max_bits 32 or 64: the widest tensor entry the key serves
- * (the tables hold 15 multiples per 4-bit window and generator: 168 B x 15 x max_bits / 4 per generator).
+ * (the tables hold 255 multiples per 8-bit window and generator: 168 B x 255 x max_bits / 8 per generator,
+ * 167 KB at 32 bits).
  * zkdl_commit_key_generators: generators first .. first + count - 1 (index ncols = H) as bytes, for checks. */
 typedef struct zkdl_commit_key zkdl_commit_key;
 int zkdl_commit_key_create(zkdl_ctx* ctx, const char* label, uint64_t ncols, int max_bits, zkdl_commit_key** out);

@@ -10,10 +10,10 @@
 //
 // Scalars are small: tensors are 32-bit (activations, weights, gradients) or 64-bit (pre-activations)
 // signed integers, a negative entry x being the field element r - |x|, i.e. -|x| G.  The sum therefore
-// runs over fixed-base window tables: for every generator the multiples d 2^(4k) G, d = 1..15, k < bits/4,
-// are built once with the key, and a commitment is a plain sum of one table entry per non-zero 4-bit digit
-// of |x| - no doublings and no buckets.  The blinding term rho H (rho a full field element) uses the same
-// kind of table with 64 windows.  All sums use the complete projective formulas of fq.cuh: a row's sum may be
+// runs over fixed-base window tables: for every generator the multiples d 2^(8k) G, d = 1..255, k < bits/8,
+// are built once with the key (167 KB per generator for 32-bit entries: memory is what this GPU has), and a
+// commitment is a plain sum of one table entry per non-zero 8-bit digit of |x| - no doublings and no buckets.
+// The blinding term rho H (rho a full field element) uses the same kind of table with 32 windows.  All sums use the complete projective formulas of fq.cuh: a row's sum may be
 // taken in any order.
 #include <string.h>
 #include <new>
@@ -24,8 +24,9 @@
 
 namespace {
 
-constexpr int CK_DIGITS = 15;        // table entries per window: d = 1..15
-constexpr int CK_H_WINDOWS = 64;     // 4-bit windows of a 255-bit blinding scalar
+constexpr int CK_WBITS = 8;                      // bits per window
+constexpr int CK_DIGITS = (1 << CK_WBITS) - 1;   // table entries per window: d = 1..255
+constexpr int CK_H_WINDOWS = 256 / CK_WBITS;     // windows of a 255-bit blinding scalar
 constexpr int CK_MAX_LABEL = 16;
 
 struct LabelArg {
@@ -106,14 +107,14 @@ __global__ __launch_bounds__(64) void k_ck_generators(LabelArg label, uint64_t n
     }
 }
 
-// table[(g * windows + k) * 15 + d - 1] = d 2^(4k) gens[g]
+// table[(g * windows + k) * CK_DIGITS + d - 1] = d 2^(CK_WBITS k) gens[g]
 __global__ __launch_bounds__(64) void k_ck_tables(const G1* gens, uint64_t ngens, int windows, G1* table) {
     const uint64_t t = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
     if (t >= ngens * (uint64_t)windows) return;
     const uint64_t g = t / windows;
     const int k = (int)(t % windows);
     G1 base = gens[g];
-    for (int s = 0; s < 4 * k; ++s) base = g1_dbl(base);
+    for (int s = 0; s < CK_WBITS * k; ++s) base = g1_dbl(base);
     G1* out = table + t * CK_DIGITS;
     G1 acc = base;
     out[0] = acc;
@@ -142,19 +143,19 @@ __device__ inline G1 g1_shfl_down(const G1& p, int off) {
 }
 
 // One wave per row: sums[row] = rho_row H + sum_c x[row, c] G_c (projective).  Lane l takes the columns
-// l, l + 64, .. and walks the non-zero 4-bit digits of their magnitudes as one stream: every trip of the loop
+// l, l + 64, .. and walks the non-zero 8-bit digits of their magnitudes as one stream: every trip of the loop
 // adds one table entry in every lane that still has a digit, whatever entry and window it belongs to, so lanes
-// do not wait for each other's zero digits.  Lane k also starts from window k of the blinding scalar.  The 64
+// do not wait for each other's zero digits.  Lane k < 32 also starts from window k of the blinding scalar.  The 64
 // partial sums are added by a shuffle tree.
 template <typename INT>
 __global__ __launch_bounds__(64) void k_commit_rows(const INT* x, uint64_t cols, int windows, const G1* table,
                                                     const uint32_t* rho_le, const G1* h_table, G1* sums) {
-    static_assert(CK_H_WINDOWS == 64, "one lane per window of the blinding scalar");
+    static_assert(CK_H_WINDOWS <= 64 && CK_WBITS == 8, "one lane per window (byte) of the blinding scalar");
     const uint64_t row = blockIdx.x;
     const int lane = threadIdx.x;
     G1 acc = g1_identity();
     if (rho_le) {
-        const uint32_t d = (rho_le[row * 8 + (lane >> 3)] >> (4 * (lane & 7))) & 15u;
+        const uint32_t d = lane < CK_H_WINDOWS ? (rho_le[row * 8 + (lane >> 2)] >> (8 * (lane & 3))) & 255u : 0u;
         if (d) acc = h_table[lane * CK_DIGITS + d - 1];
     }
     const INT* xr = x + row * cols;
@@ -176,19 +177,19 @@ __global__ __launch_bounds__(64) void k_commit_rows(const INT* x, uint64_t cols,
                 c += 64;
                 continue;
             }
-            const int skip = (__ffsll((unsigned long long)mag) - 1) >> 2;
-            mag >>= 4 * skip;
+            const int skip = (__ffsll((unsigned long long)mag) - 1) / CK_WBITS;
+            mag >>= CK_WBITS * skip;
             k += skip;
             active = true;
             break;
         }
         if (__ballot(active) == 0) break;   // no lane has a digit left
         if (active) {
-            const uint32_t d = (uint32_t)mag & 15u;
+            const uint32_t d = (uint32_t)mag & (uint32_t)CK_DIGITS;
             G1 p = table[(c * (uint64_t)windows + (uint64_t)k) * CK_DIGITS + d - 1];
             if (negative) p.Y = fq_neg(p.Y);   // x = r - |x| as a field element: -|x| G
             acc = g1_add_ni(acc, p);
-            mag >>= 4;
+            mag >>= CK_WBITS;
             ++k;
         }
     }
@@ -427,10 +428,10 @@ __global__ __launch_bounds__(64) void k_ck_export(const G1* gens, uint64_t first
 
 struct zkdl_commit_key {
     uint64_t ncols;
-    int windows;      // 4-bit windows of a tensor entry: 8 (32-bit) or 16 (64-bit)
+    int windows;      // 8-bit windows of a tensor entry: 4 (32-bit) or 8 (64-bit)
     G1* gens;         // device: ncols generators, then H
-    G1* table;        // device: [ncols][windows][15]
-    G1* h_table;      // device: [64][15]
+    G1* table;        // device: [ncols][windows][255]
+    G1* h_table;      // device: [32][255]
 };
 
 // host-side check of the constants of fq.cuh (no GPU needed): Montgomery one and R^2 by repeated doubling,
@@ -485,7 +486,7 @@ extern "C" int zkdl_commit_key_create(zkdl_ctx* ctx, const char* label, uint64_t
     zkdl_commit_key* key = new (std::nothrow) zkdl_commit_key();
     if (!key) return ZKDL_ENOMEM;
     key->ncols = ncols;
-    key->windows = max_bits / 4;
+    key->windows = max_bits / CK_WBITS;
     key->gens = (G1*)zk_alloc(ctx, sizeof(G1) * (ncols + 1));
     key->table = (G1*)zk_alloc(ctx, sizeof(G1) * ncols * key->windows * CK_DIGITS);
     key->h_table = (G1*)zk_alloc(ctx, sizeof(G1) * CK_H_WINDOWS * CK_DIGITS);
@@ -533,7 +534,7 @@ extern "C" int hyrax_commit(zkdl_ctx* ctx, const zkdl_commit_key* key, const zkd
                             uint8_t* commitments_out, size_t* ncommit) {
     if (!ctx || !key || !X || !commitments_out || !ncommit) return ZKDL_EINVAL;
     if (X->kind != TK_I32 && X->kind != TK_I64) return ZKDL_EINVAL;
-    if (X->kind == TK_I64 && key->windows < 16) return ZKDL_EINVAL;
+    if (X->kind == TK_I64 && key->windows < 64 / CK_WBITS) return ZKDL_EINVAL;
     int m = 0;
     while (((uint64_t)1 << m) < X->numel) ++m;
     if (((uint64_t)1 << m) != X->numel) return ZKDL_EINVAL;
