@@ -128,8 +128,10 @@ FQ_HD Fq fq_sub(const Fq& a, const Fq& b) {
 
 FQ_HD Fq fq_neg(const Fq& a) { return fq_sub(fq_zero(), a); }
 
-// Montgomery product a b / 2^406 mod q, fully reduced; a, b below q
-FQ_HD Fq fq_mul(const Fq& a, const Fq& b) {
+// Montgomery product a b / 2^406 mod q for operands with normal limbs and a b < q 2^406 (any a, b below 2^12 q):
+// the value before the last step is below a b / 2^406 + q < 2q; REDUCE takes q off it if it is not below q
+template <bool REDUCE>
+FQ_HD Fq fq_mul_t(const Fq& a, const Fq& b) {
     uint64_t acc = 0;
     uint32_t m[fqc::L];
     Fq t;
@@ -150,8 +152,11 @@ FQ_HD Fq fq_mul(const Fq& a, const Fq& b) {
         acc >>= 29;
     }
     t.v[fqc::L - 1] = (uint32_t)acc;
-    return fq_cond_sub(t);   // a b / R + q < 2q
+    return REDUCE ? fq_cond_sub(t) : t;
 }
+
+// fully reduced; a, b below q (or as above)
+FQ_HD Fq fq_mul(const Fq& a, const Fq& b) { return fq_mul_t<true>(a, b); }
 
 FQ_HD Fq fq_sqr(const Fq& a) { return fq_mul(a, a); }
 
@@ -378,6 +383,116 @@ struct FqMulInline {
 };
 
 FQ_HD G1 g1_add(const G1& p, const G1& q) { return g1_add_with(p, q, FqMulInline()); }
+
+// ---- the same addition without reductions ----------------------------------------------------------------------
+// For long sums of points: coordinates are kept below 6q with normal limbs instead of below q.  Sums are carried but
+// not reduced, differences are shifted by a multiple of q that is spread over the limbs so that no limb borrows,
+// small multiples go through one carry pass, and the product skips its conditional subtraction (its result is
+// below 2q for every pair of operands that occurs here: the largest product of bounds is 120q x 10q, far below
+// q 2^406 / q = 2^25 q).  About a quarter fewer instructions per addition than with every value reduced.
+namespace fqc {
+struct Limbs {
+    uint32_t v[L];
+};
+constexpr Limbs times_q(uint32_t k) {   // normal limbs of k q
+    Limbs o{};
+    uint64_t c = 0;
+    for (int i = 0; i < L; ++i) {
+        const uint64_t x = (uint64_t)Q[i] * k + c;
+        o.v[i] = i < L - 1 ? (uint32_t)(x & M29) : (uint32_t)x;
+        c = x >> 29;
+    }
+    return o;
+}
+// k q with 2^30 lent to every limb below the top one and taken back, as 2, from the limb above: two normal limbs can
+// be taken from each of these limbs without a borrow
+constexpr Limbs spread_q(uint32_t k) {
+    Limbs o = times_q(k);
+    for (int i = 0; i < L - 1; ++i) {
+        o.v[i] += 1u << 30;
+        o.v[i + 1] -= 2;
+    }
+    return o;
+}
+}  // namespace fqc
+
+FQ_HD Fq fq_add_lazy(const Fq& a, const Fq& b) {
+    Fq o;
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        const uint32_t x = a.v[i] + b.v[i] + c;
+        o.v[i] = i < fqc::L - 1 ? (x & fqc::M29) : x;
+        c = i < fqc::L - 1 ? (x >> 29) : 0;
+    }
+    return o;
+}
+
+// a - b - c + K q for b + c below SUB q (c may be zero); the result is below a + K q
+template <uint32_t K, uint32_t SUB>
+FQ_HD Fq fq_sub2_lazy(const Fq& a, const Fq& b, const Fq& c) {
+    constexpr fqc::Limbs C = fqc::spread_q(K);
+    static_assert(K >= SUB && C.v[fqc::L - 1] < (1u << 29) && C.v[fqc::L - 1] >= fqc::times_q(SUB).v[fqc::L - 1] + 1,
+                  "the top limb of K q covers the top limbs taken from it");
+    Fq o;
+    uint32_t carry = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        const uint32_t x = a.v[i] + C.v[i] - b.v[i] - c.v[i] + carry;
+        o.v[i] = i < fqc::L - 1 ? (x & fqc::M29) : x;
+        carry = i < fqc::L - 1 ? (x >> 29) : 0;
+    }
+    return o;
+}
+
+template <uint32_t K>
+FQ_HD Fq fq_times_lazy(const Fq& a) {   // K a, K small
+    Fq o;
+    uint64_t c = 0;
+#pragma unroll
+    for (int i = 0; i < fqc::L; ++i) {
+        const uint64_t x = (uint64_t)a.v[i] * K + c;
+        o.v[i] = i < fqc::L - 1 ? ((uint32_t)x & fqc::M29) : (uint32_t)x;
+        c = x >> 29;
+    }
+    return o;
+}
+
+// p + q for coordinates below 6q (normal limbs); the result's are below 6q again.  `mul` is the product WITHOUT the
+// conditional subtraction (results below 2q).
+template <class Mul>
+FQ_HD G1 g1_add_lazy_with(const G1& p, const G1& q, Mul mul) {
+    const Fq zero = fq_zero();
+    const Fq t0 = mul(p.X, q.X), t1 = mul(p.Y, q.Y), t2 = mul(p.Z, q.Z);                 // below 2q
+    const Fq p3 = mul(fq_add_lazy(p.X, p.Y), fq_add_lazy(q.X, q.Y));                      // 12q x 12q
+    const Fq p4 = mul(fq_add_lazy(p.Y, p.Z), fq_add_lazy(q.Y, q.Z));
+    const Fq p5 = mul(fq_add_lazy(p.X, p.Z), fq_add_lazy(q.X, q.Z));
+    const Fq t3 = fq_sub2_lazy<8, 4>(p3, t0, t1);                                         // X1Y2 + X2Y1, in (4q, 10q)
+    const Fq t4 = fq_sub2_lazy<8, 4>(p4, t1, t2);                                         // Y1Z2 + Y2Z1
+    const Fq y3 = fq_times_lazy<12>(fq_sub2_lazy<8, 4>(p5, t0, t2));                      // 12 (X1Z2 + X2Z1), below 120q
+    const Fq x3 = fq_times_lazy<3>(t0);                                                   // below 6q
+    const Fq t2b = fq_times_lazy<12>(t2);                                                 // below 24q
+    const Fq z3 = fq_add_lazy(t1, t2b);                                                   // below 26q
+    const Fq t1b = fq_sub2_lazy<32, 24>(t1, t2b, zero);                                   // in (8q, 34q)
+    G1 r;
+    r.X = fq_sub2_lazy<4, 2>(mul(t3, t1b), mul(t4, y3), zero);                            // below 6q
+    r.Y = fq_add_lazy(mul(t1b, z3), mul(y3, x3));                                         // below 4q
+    r.Z = fq_add_lazy(mul(z3, t4), mul(x3, t3));
+    return r;
+}
+
+struct FqMulLazyInline {
+    FQ_HD Fq operator()(const Fq& a, const Fq& b) const { return fq_mul_t<false>(a, b); }
+};
+
+// coordinates with normal limbs, any value below 2^12 q -> below q
+FQ_HD G1 g1_reduce(const G1& p) {
+    G1 r;
+    r.X = fq_mul(p.X, fq_one());
+    r.Y = fq_mul(p.Y, fq_one());
+    r.Z = fq_mul(p.Z, fq_one());
+    return r;
+}
 
 // doubling (Algorithm 9, a = 0)
 template <class Mul>

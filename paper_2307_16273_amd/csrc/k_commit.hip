@@ -126,10 +126,12 @@ __global__ __launch_bounds__(64) void k_ck_tables(const G1* gens, uint64_t ngens
 
 // one copy of the 406-multiply-add field product for the kernels that add points in a loop
 __device__ __noinline__ Fq fq_mul_ni(Fq a, Fq b) { return fq_mul(a, b); }
-struct FqMulOutOfLine {
-    __device__ Fq operator()(const Fq& a, const Fq& b) const { return fq_mul_ni(a, b); }
+// the same for the addition without reductions (coordinates below 6q)
+__device__ __noinline__ Fq fq_mul_lazy_ni(Fq a, Fq b) { return fq_mul_t<false>(a, b); }
+struct FqMulLazyOutOfLine {
+    __device__ Fq operator()(const Fq& a, const Fq& b) const { return fq_mul_lazy_ni(a, b); }
 };
-__device__ inline G1 g1_add_ni(const G1& p, const G1& q) { return g1_add_with(p, q, FqMulOutOfLine()); }
+__device__ inline G1 g1_add_lazy_ni(const G1& p, const G1& q) { return g1_add_lazy_with(p, q, FqMulLazyOutOfLine()); }
 
 __device__ inline G1 g1_shfl_down(const G1& p, int off) {
     G1 q;
@@ -146,7 +148,8 @@ __device__ inline G1 g1_shfl_down(const G1& p, int off) {
 // l, l + 64, .. and walks the non-zero 8-bit digits of their magnitudes as one stream: every trip of the loop
 // adds one table entry in every lane that still has a digit, whatever entry and window it belongs to, so lanes
 // do not wait for each other's zero digits.  Lane k < 32 also starts from window k of the blinding scalar.  The 64
-// partial sums are added by a shuffle tree.
+// partial sums are added by a shuffle tree.  The additions skip every reduction (g1_add_lazy_with): the running sum's
+// coordinates stay below 6q, the table entries are below q.
 template <typename INT>
 __global__ __launch_bounds__(64) void k_commit_rows(const INT* x, uint64_t cols, int windows, const G1* table,
                                                     const uint32_t* rho_le, const G1* h_table, G1* sums) {
@@ -188,21 +191,21 @@ __global__ __launch_bounds__(64) void k_commit_rows(const INT* x, uint64_t cols,
             const uint32_t d = (uint32_t)mag & (uint32_t)CK_DIGITS;
             G1 p = table[(c * (uint64_t)windows + (uint64_t)k) * CK_DIGITS + d - 1];
             if (negative) p.Y = fq_neg(p.Y);   // x = r - |x| as a field element: -|x| G
-            acc = g1_add_ni(acc, p);
+            acc = g1_add_lazy_ni(acc, p);
             mag >>= CK_WBITS;
             ++k;
         }
     }
 #pragma unroll 1
-    for (int off = 32; off >= 1; off >>= 1) acc = g1_add_ni(acc, g1_shfl_down(acc, off));
-    if (lane == 0) sums[row] = acc;
+    for (int off = 32; off >= 1; off >>= 1) acc = g1_add_lazy_ni(acc, g1_shfl_down(acc, off));
+    if (lane == 0) sums[row] = acc;   // coordinates below 6q
 }
 
 // affine bytes of the row sums: one inversion per row, one lane per row
 __global__ __launch_bounds__(64) void k_commit_affine(const G1* sums, uint64_t rows, uint8_t* out) {
     const uint64_t row = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
     if (row >= rows) return;
-    g1_to_bytes(sums[row], out + row * 96);
+    g1_to_bytes(g1_reduce(sums[row]), out + row * 96);
 }
 
 // ---- the verifier's side of an opening: two sums of scalar multiples with full field elements as scalars ----
