@@ -481,6 +481,27 @@ FQ_HD G1 g1_add_lazy_with(const G1& p, const G1& q, Mul mul) {
     return r;
 }
 
+// The same with the second point affine (x2, y2; never the identity; x2 below q, y2 at most 2q): eleven products
+// (Algorithm 8 of the same reference, a = 0).
+template <class Mul>
+FQ_HD G1 g1_add_mixed_lazy_with(const G1& p, const Fq& x2, const Fq& y2, Mul mul) {
+    const Fq zero = fq_zero();
+    const Fq t0 = mul(p.X, x2), t1 = mul(p.Y, y2);                                        // below 2q
+    const Fq p3 = mul(fq_add_lazy(p.X, p.Y), fq_add_lazy(x2, y2));                        // 12q x 3q
+    const Fq t3 = fq_sub2_lazy<8, 4>(p3, t0, t1);                                         // X1 y2 + x2 Y1, in (4q, 10q)
+    const Fq t4 = fq_add_lazy(mul(y2, p.Z), p.Y);                                         // y2 Z1 + Y1, below 8q
+    const Fq y3 = fq_times_lazy<12>(fq_add_lazy(mul(x2, p.Z), p.X));                      // 12 (x2 Z1 + X1), below 96q
+    const Fq x3 = fq_times_lazy<3>(t0);                                                   // below 6q
+    const Fq t2b = fq_times_lazy<12>(p.Z);                                                // below 72q
+    const Fq z3 = fq_add_lazy(t1, t2b);                                                   // below 74q
+    const Fq t1b = fq_sub2_lazy<80, 72>(t1, t2b, zero);                                   // in (8q, 82q)
+    G1 r;
+    r.X = fq_sub2_lazy<4, 2>(mul(t3, t1b), mul(t4, y3), zero);                            // below 6q
+    r.Y = fq_add_lazy(mul(t1b, z3), mul(y3, x3));                                         // below 4q
+    r.Z = fq_add_lazy(mul(z3, t4), mul(x3, t3));
+    return r;
+}
+
 struct FqMulLazyInline {
     FQ_HD Fq operator()(const Fq& a, const Fq& b) const { return fq_mul_t<false>(a, b); }
 };

@@ -107,31 +107,62 @@ __global__ __launch_bounds__(64) void k_ck_generators(LabelArg label, uint64_t n
     }
 }
 
-// table[(g * windows + k) * CK_DIGITS + d - 1] = d 2^(CK_WBITS k) gens[g]
-__global__ __launch_bounds__(64) void k_ck_tables(const G1* gens, uint64_t ngens, int windows, G1* table) {
+// one copy of the 406-multiply-add field product for the kernels that add points in a loop
+__device__ __noinline__ Fq fq_mul_ni(Fq a, Fq b) { return fq_mul(a, b); }
+struct FqMulOutOfLine {
+    __device__ Fq operator()(const Fq& a, const Fq& b) const { return fq_mul_ni(a, b); }
+};
+
+struct G1A {   // affine, never the identity
+    Fq x, y;
+};
+constexpr int CK_CHUNK = 16;   // table entries per thread of k_ck_tables
+
+// table[(g * windows + k) * CK_DIGITS + d - 1] = d 2^(CK_WBITS k) gens[g], affine.  One thread per (g, k, 16 digits):
+// the window's base by doublings, 16 c times the base by double-and-add, then one addition and one inversion per
+// entry.
+__global__ __launch_bounds__(64) void k_ck_tables(const G1* gens, uint64_t ngens, int windows, G1A* table) {
     const uint64_t t = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
-    if (t >= ngens * (uint64_t)windows) return;
-    const uint64_t g = t / windows;
-    const int k = (int)(t % windows);
+    constexpr int chunks = (CK_DIGITS + 1) / CK_CHUNK;
+    const uint64_t gk = t / chunks;
+    const int chunk = (int)(t % chunks);
+    if (gk >= ngens * (uint64_t)windows) return;
+    const uint64_t g = gk / windows;
+    const int k = (int)(gk % windows);
+    const FqMulOutOfLine mul;
     G1 base = gens[g];
-    for (int s = 0; s < CK_WBITS * k; ++s) base = g1_dbl(base);
-    G1* out = table + t * CK_DIGITS;
-    G1 acc = base;
-    out[0] = acc;
-    for (int d = 2; d <= CK_DIGITS; ++d) {
-        acc = g1_add(acc, base);
-        out[d - 1] = acc;
+#pragma unroll 1
+    for (int s = 0; s < CK_WBITS * k; ++s) base = g1_dbl_with(base, mul);
+    const int first = CK_CHUNK * chunk;
+    G1 acc = g1_identity();
+#pragma unroll 1
+    for (int bit = CK_WBITS - 1; bit >= 0; --bit) {
+        acc = g1_dbl_with(acc, mul);
+        if ((first >> bit) & 1) acc = g1_add_with(acc, base, mul);
+    }
+    G1A* out = table + gk * CK_DIGITS;
+#pragma unroll 1
+    for (int d = first; d < first + CK_CHUNK; ++d) {   // acc = d base
+        if (d) {
+            const Fq zi = fq_inv_euclid(acc.Z);
+            G1A e;
+            e.x = fq_mul_ni(acc.X, zi);
+            e.y = fq_mul_ni(acc.Y, zi);
+            out[d - 1] = e;
+        }
+        acc = g1_add_with(acc, base, mul);
     }
 }
 
-// one copy of the 406-multiply-add field product for the kernels that add points in a loop
-__device__ __noinline__ Fq fq_mul_ni(Fq a, Fq b) { return fq_mul(a, b); }
-// the same for the addition without reductions (coordinates below 6q)
+// the product without its conditional subtraction, for the additions without reductions (coordinates below 6q)
 __device__ __noinline__ Fq fq_mul_lazy_ni(Fq a, Fq b) { return fq_mul_t<false>(a, b); }
 struct FqMulLazyOutOfLine {
     __device__ Fq operator()(const Fq& a, const Fq& b) const { return fq_mul_lazy_ni(a, b); }
 };
 __device__ inline G1 g1_add_lazy_ni(const G1& p, const G1& q) { return g1_add_lazy_with(p, q, FqMulLazyOutOfLine()); }
+__device__ inline G1 g1_add_mixed_lazy_ni(const G1& p, const Fq& x2, const Fq& y2) {
+    return g1_add_mixed_lazy_with(p, x2, y2, FqMulLazyOutOfLine());
+}
 
 __device__ inline G1 g1_shfl_down(const G1& p, int off) {
     G1 q;
@@ -148,18 +179,23 @@ __device__ inline G1 g1_shfl_down(const G1& p, int off) {
 // l, l + 64, .. and walks the non-zero 8-bit digits of their magnitudes as one stream: every trip of the loop
 // adds one table entry in every lane that still has a digit, whatever entry and window it belongs to, so lanes
 // do not wait for each other's zero digits.  Lane k < 32 also starts from window k of the blinding scalar.  The 64
-// partial sums are added by a shuffle tree.  The additions skip every reduction (g1_add_lazy_with): the running sum's
-// coordinates stay below 6q, the table entries are below q.
+// partial sums are added by a shuffle tree.  The additions skip every reduction: the running sum's coordinates stay
+// below 6q; the table entries are affine and below q, so an addition in the loop has eleven products.
 template <typename INT>
-__global__ __launch_bounds__(64) void k_commit_rows(const INT* x, uint64_t cols, int windows, const G1* table,
-                                                    const uint32_t* rho_le, const G1* h_table, G1* sums) {
+__global__ __launch_bounds__(64) void k_commit_rows(const INT* x, uint64_t cols, int windows, const G1A* table,
+                                                    const uint32_t* rho_le, const G1A* h_table, G1* sums) {
     static_assert(CK_H_WINDOWS <= 64 && CK_WBITS == 8, "one lane per window (byte) of the blinding scalar");
     const uint64_t row = blockIdx.x;
     const int lane = threadIdx.x;
     G1 acc = g1_identity();
     if (rho_le) {
         const uint32_t d = lane < CK_H_WINDOWS ? (rho_le[row * 8 + (lane >> 2)] >> (8 * (lane & 3))) & 255u : 0u;
-        if (d) acc = h_table[lane * CK_DIGITS + d - 1];
+        if (d) {
+            const G1A e = h_table[lane * CK_DIGITS + d - 1];
+            acc.X = e.x;
+            acc.Y = e.y;
+            acc.Z = fq_one();
+        }
     }
     const INT* xr = x + row * cols;
     uint64_t c = (uint64_t)lane, mag = 0;
@@ -189,9 +225,12 @@ __global__ __launch_bounds__(64) void k_commit_rows(const INT* x, uint64_t cols,
         if (__ballot(active) == 0) break;   // no lane has a digit left
         if (active) {
             const uint32_t d = (uint32_t)mag & (uint32_t)CK_DIGITS;
-            G1 p = table[(c * (uint64_t)windows + (uint64_t)k) * CK_DIGITS + d - 1];
-            if (negative) p.Y = fq_neg(p.Y);   // x = r - |x| as a field element: -|x| G
-            acc = g1_add_lazy_ni(acc, p);
+            const G1A e = table[(c * (uint64_t)windows + (uint64_t)k) * CK_DIGITS + d - 1];
+            const Fq yn = fq_sub2_lazy<2, 1>(fq_zero(), e.y, fq_zero());   // 2q - y: x = r - |x| as a field element is -|x| G
+            Fq y2;
+#pragma unroll
+            for (int i = 0; i < fqc::L; ++i) y2.v[i] = negative ? yn.v[i] : e.y.v[i];
+            acc = g1_add_mixed_lazy_ni(acc, e.x, y2);
             mag >>= CK_WBITS;
             ++k;
         }
@@ -433,8 +472,8 @@ struct zkdl_commit_key {
     uint64_t ncols;
     int windows;      // 8-bit windows of a tensor entry: 4 (32-bit) or 8 (64-bit)
     G1* gens;         // device: ncols generators, then H
-    G1* table;        // device: [ncols][windows][255]
-    G1* h_table;      // device: [32][255]
+    G1A* table;       // device: [ncols][windows][255], affine
+    G1A* h_table;     // device: [32][255]
 };
 
 // host-side check of the constants of fq.cuh (no GPU needed): Montgomery one and R^2 by repeated doubling,
@@ -466,6 +505,59 @@ extern "C" int zkdl_commit_selfcheck(void) {
     for (int i = 0; i < 16; ++i)
         if (!fq_eq(fq_inv_euclid(probe[i]), fq_inv(probe[i]))) return ZKDL_EINVAL;
     if (!fq_is_zero(fq_inv_euclid(fq_zero()))) return ZKDL_EINVAL;
+    // the additions without reductions against the reduced one, on multiples of a point found by trying x = 1, 2, ..:
+    // a running sum that only ever goes through the lazy forms (so its coordinates take the bounds the kernel's do),
+    // the sum from the identity, a point added to itself and to its negative
+    G1 base = g1_identity();
+    Fq xs = fq_zero();
+    const Fq four = fq_add(fq_add(fq_one(), fq_one()), fq_add(fq_one(), fq_one()));
+    for (int t = 0; t < 64 && fq_is_zero(base.Z); ++t) {
+        xs = fq_add(xs, fq_one());
+        const Fq rhs = fq_add(fq_mul(fq_sqr(xs), xs), four);
+        const Fq y = fq_pow(rhs, fqc::EXP_SQRT);
+        if (fq_eq(fq_sqr(y), rhs) && !fq_is_zero(y)) {
+            base.X = xs;
+            base.Y = y;
+            base.Z = fq_one();
+        }
+    }
+    if (fq_is_zero(base.Z)) return ZKDL_EINVAL;
+    auto same = [](const G1& a, const G1& b) {   // equal as projective points, coordinates reduced
+        return fq_eq(fq_mul(a.X, b.Z), fq_mul(b.X, a.Z)) && fq_eq(fq_mul(a.Y, b.Z), fq_mul(b.Y, a.Z)) &&
+               fq_is_zero(a.Z) == fq_is_zero(b.Z);
+    };
+    auto affine = [](const G1& p, Fq* x, Fq* y) {
+        const Fq zi = fq_inv_euclid(p.Z);
+        *x = fq_mul(p.X, zi);
+        *y = fq_mul(p.Y, zi);
+    };
+    const FqMulLazyInline lazy;
+    G1 term = base, sum = g1_identity(), lsum = g1_identity(), msum = g1_identity();
+    for (int i = 0; i < 40; ++i) {
+        Fq tx, ty;
+        affine(term, &tx, &ty);
+        Fq y2 = ty;
+        if (i % 3 == 1) {   // every third term negated the way the kernel negates (2q - y)
+            term = g1_neg(term);
+            y2 = fq_sub2_lazy<2, 1>(fq_zero(), ty, fq_zero());
+        }
+        sum = g1_add(sum, term);
+        lsum = g1_add_lazy_with(lsum, term, lazy);
+        msum = g1_add_mixed_lazy_with(msum, tx, y2, lazy);
+        if (!same(g1_reduce(lsum), sum) || !same(g1_reduce(msum), sum)) return ZKDL_EINVAL;
+        if (!same(g1_reduce(g1_add_lazy_with(lsum, msum, lazy)), g1_dbl(sum))) return ZKDL_EINVAL;   // two lazy operands
+        term = g1_add(g1_dbl(term), base);
+    }
+    {
+        Fq bx, by;
+        affine(base, &bx, &by);
+        const Fq byn = fq_sub2_lazy<2, 1>(fq_zero(), by, fq_zero());
+        if (!same(g1_reduce(g1_add_mixed_lazy_with(base, bx, by, lazy)), g1_dbl(base))) return ZKDL_EINVAL;
+        const G1 o = g1_reduce(g1_add_mixed_lazy_with(base, bx, byn, lazy));
+        if (!fq_is_zero(o.Z) || !fq_is_zero(o.X)) return ZKDL_EINVAL;
+        const G1 o2 = g1_reduce(g1_add_lazy_with(base, g1_neg(base), lazy));
+        if (!fq_is_zero(o2.Z) || !fq_is_zero(o2.X)) return ZKDL_EINVAL;
+    }
     return ZKDL_OK;
 }
 
@@ -491,8 +583,8 @@ extern "C" int zkdl_commit_key_create(zkdl_ctx* ctx, const char* label, uint64_t
     key->ncols = ncols;
     key->windows = max_bits / CK_WBITS;
     key->gens = (G1*)zk_alloc(ctx, sizeof(G1) * (ncols + 1));
-    key->table = (G1*)zk_alloc(ctx, sizeof(G1) * ncols * key->windows * CK_DIGITS);
-    key->h_table = (G1*)zk_alloc(ctx, sizeof(G1) * CK_H_WINDOWS * CK_DIGITS);
+    key->table = (G1A*)zk_alloc(ctx, sizeof(G1A) * ncols * key->windows * CK_DIGITS);
+    key->h_table = (G1A*)zk_alloc(ctx, sizeof(G1A) * CK_H_WINDOWS * CK_DIGITS);
     if (!key->gens || !key->table || !key->h_table) {
         zkdl_commit_key_destroy(ctx, key);
         return ZKDL_ENOMEM;
@@ -504,11 +596,12 @@ extern "C" int zkdl_commit_key_create(zkdl_ctx* ctx, const char* label, uint64_t
     const Fq r2x = r2x_const();
     hipLaunchKernelGGL(k_ck_generators, dim3((unsigned)((ncols + 1 + 63) / 64)), dim3(64), 0, ctx->stream, la, ncols,
                        key->gens, r2x);
-    const uint64_t nt = ncols * key->windows;
+    constexpr uint64_t chunks = (CK_DIGITS + 1) / CK_CHUNK;   // threads per (generator, window)
+    const uint64_t nt = ncols * key->windows * chunks, nh = (uint64_t)CK_H_WINDOWS * chunks;
     hipLaunchKernelGGL(k_ck_tables, dim3((unsigned)((nt + 63) / 64)), dim3(64), 0, ctx->stream, key->gens, ncols,
                        key->windows, key->table);
-    hipLaunchKernelGGL(k_ck_tables, dim3(1), dim3(64), 0, ctx->stream, key->gens + ncols, (uint64_t)1, CK_H_WINDOWS,
-                       key->h_table);
+    hipLaunchKernelGGL(k_ck_tables, dim3((unsigned)((nh + 63) / 64)), dim3(64), 0, ctx->stream, key->gens + ncols,
+                       (uint64_t)1, CK_H_WINDOWS, key->h_table);
     hipError_t e = hipStreamSynchronize(ctx->stream);
     if (e == hipSuccess) e = hipGetLastError();
     if (e != hipSuccess) {
