@@ -13,7 +13,7 @@ ERRORS = {0: "ok", -1: "ZKDL_EINVAL", -2: "ZKDL_ERANGE", -3: "ZKDL_ENOMEM", -4: 
 
 EXPORTED_SYMBOLS = [
     "zkdl_ctx_create", "zkdl_ctx_destroy", "zkdl_last_hip_error", "zkdl_strerror", "zkdl_ctx_trim",
-    "zkdl_ctx_set_fill_threads",
+    "zkdl_ctx_set_fill_threads", "zkdl_ctx_set_commit_window_bits",
     "zkdl_transcript_create", "zkdl_transcript_destroy", "zkdl_transcript_absorb",
     "zkdl_transcript_challenge", "zkdl_transcript_digest",
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
@@ -72,6 +72,7 @@ def load_library():
     sig = {
         "zkdl_ctx_create": [pp, i, vp], "zkdl_ctx_destroy": [vp], "zkdl_last_hip_error": [vp],
         "zkdl_ctx_trim": [vp], "zkdl_ctx_set_fill_threads": [vp, u64],
+        "zkdl_ctx_set_commit_window_bits": [vp, i],
         "zkdl_transcript_create": [pp, u64], "zkdl_transcript_destroy": [vp],
         "zkdl_transcript_absorb": [vp, C.c_char_p, vp, sz], "zkdl_transcript_challenge": [vp, vp],
         "zkdl_transcript_digest": [vp, vp],
@@ -172,6 +173,10 @@ class Context:
 
     def set_fill_threads(self, threads):
         _check(load_library().zkdl_ctx_set_fill_threads(self.handle, int(threads)), "zkdl_ctx_set_fill_threads", self)
+
+    def set_commit_window_bits(self, bits):
+        _check(load_library().zkdl_ctx_set_commit_window_bits(self.handle, int(bits)),
+               "zkdl_ctx_set_commit_window_bits", self)
 
     def close(self):
         if self.handle:

@@ -164,6 +164,7 @@ extern "C" int zkdl_ctx_create(zkdl_ctx** out, int device, void* hip_stream) {
     ctx->n_chal = 0;
     ctx->proof_len = 0;
     ctx->prof_on = false;
+    ctx->commit_wbits = 0;
     ctx->zk_fill_threads = 65536;    // one wave on each of the 1024 SIMDs; measured best on the 8 x 1024^2 network
     ctx->prof_used = 0;
     for (int i = 0; i < ZKDL_PROF_CLASSES; ++i) {
@@ -227,6 +228,12 @@ extern "C" int zkdl_last_hip_error(const zkdl_ctx* ctx) { return ctx ? ctx->last
 extern "C" int zkdl_ctx_set_fill_threads(zkdl_ctx* ctx, uint64_t threads) {
     if (!ctx || threads < 1 || threads > ((uint64_t)1 << 24)) return ZKDL_EINVAL;
     ctx->zk_fill_threads = threads;
+    return ZKDL_OK;
+}
+
+extern "C" int zkdl_ctx_set_commit_window_bits(zkdl_ctx* ctx, int bits) {
+    if (!ctx || (bits != 0 && bits != 8 && bits != 12)) return ZKDL_EINVAL;
+    ctx->commit_wbits = bits;
     return ZKDL_OK;
 }
 

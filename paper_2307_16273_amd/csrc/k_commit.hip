@@ -10,9 +10,10 @@
 //
 // Scalars are small: tensors are 32-bit (activations, weights, gradients) or 64-bit (pre-activations)
 // signed integers, a negative entry x being the field element r - |x|, i.e. -|x| G.  The sum therefore
-// runs over fixed-base window tables: for every generator the multiples d 2^(8k) G, d = 1..255, k < bits/8,
-// are built once with the key (167 KB per generator for 32-bit entries: memory is what this GPU has), and a
-// commitment is a plain sum of one table entry per non-zero 8-bit digit of |x| - no doublings and no buckets.
+// runs over fixed-base window tables: for every generator the multiples d 2^(wk) G, d = 1..2^w - 1, k < bits/w,
+// are built once with the key, in affine form (96 bytes an entry), and a commitment is a plain sum of one table
+// entry per non-zero w-bit digit of |x| - no doublings and no buckets.  w = 12 while the tables stay below 8 GiB
+// (1.2 MB per generator for 32-bit entries, 2.4 GB for 2048 columns: memory is what this GPU has), else w = 8.
 // The blinding term rho H (rho a full field element) uses the same kind of table with 32 windows.  All sums use the complete projective formulas of fq.cuh: a row's sum may be
 // taken in any order.
 #include <string.h>
@@ -24,9 +25,11 @@
 
 namespace {
 
-constexpr int CK_WBITS = 8;                      // bits per window
-constexpr int CK_DIGITS = (1 << CK_WBITS) - 1;   // table entries per window: d = 1..255
+constexpr int CK_WBITS = 8;                      // bits per window of the blinding scalar's table
+constexpr int CK_DIGITS = (1 << CK_WBITS) - 1;   // its entries per window: d = 1..255
 constexpr int CK_H_WINDOWS = 256 / CK_WBITS;     // windows of a 255-bit blinding scalar
+constexpr int CK_WIDE_WBITS = 12;                // bits per window of a tensor entry when the tables fit CK_WIDE_MAX_BYTES
+constexpr uint64_t CK_WIDE_MAX_BYTES = (uint64_t)8 << 30;
 constexpr int CK_MAX_LABEL = 16;
 
 struct LabelArg {
@@ -118,12 +121,13 @@ struct G1A {   // affine, never the identity
 };
 constexpr int CK_CHUNK = 16;   // table entries per thread of k_ck_tables
 
-// table[(g * windows + k) * CK_DIGITS + d - 1] = d 2^(CK_WBITS k) gens[g], affine.  One thread per (g, k, 16 digits):
-// the window's base by doublings, 16 c times the base by double-and-add, then one addition and one inversion per
-// entry.
-__global__ __launch_bounds__(64) void k_ck_tables(const G1* gens, uint64_t ngens, int windows, G1A* table) {
+// table[(g * windows + k) * digits + d - 1] = d 2^(wbits k) gens[g], affine, digits = 2^wbits - 1.  One thread per
+// (g, k, 16 digits): the window's base by doublings, 16 c times the base by double-and-add, then one addition and one
+// inversion per entry.
+__global__ __launch_bounds__(64) void k_ck_tables(const G1* gens, uint64_t ngens, int windows, int wbits, G1A* table) {
     const uint64_t t = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
-    constexpr int chunks = (CK_DIGITS + 1) / CK_CHUNK;
+    const int digits = (1 << wbits) - 1;
+    const int chunks = (digits + 1) / CK_CHUNK;
     const uint64_t gk = t / chunks;
     const int chunk = (int)(t % chunks);
     if (gk >= ngens * (uint64_t)windows) return;
@@ -132,15 +136,15 @@ __global__ __launch_bounds__(64) void k_ck_tables(const G1* gens, uint64_t ngens
     const FqMulOutOfLine mul;
     G1 base = gens[g];
 #pragma unroll 1
-    for (int s = 0; s < CK_WBITS * k; ++s) base = g1_dbl_with(base, mul);
+    for (int s = 0; s < wbits * k; ++s) base = g1_dbl_with(base, mul);
     const int first = CK_CHUNK * chunk;
     G1 acc = g1_identity();
 #pragma unroll 1
-    for (int bit = CK_WBITS - 1; bit >= 0; --bit) {
+    for (int bit = wbits - 1; bit >= 0; --bit) {
         acc = g1_dbl_with(acc, mul);
         if ((first >> bit) & 1) acc = g1_add_with(acc, base, mul);
     }
-    G1A* out = table + gk * CK_DIGITS;
+    G1A* out = table + gk * (uint64_t)digits;
 #pragma unroll 1
     for (int d = first; d < first + CK_CHUNK; ++d) {   // acc = d base
         if (d) {
@@ -175,16 +179,22 @@ __device__ inline G1 g1_shfl_down(const G1& p, int off) {
     return q;
 }
 
-// One wave per row: sums[row] = rho_row H + sum_c x[row, c] G_c (projective).  Lane l takes the columns
-// l, l + 64, .. and walks the non-zero 8-bit digits of their magnitudes as one stream: every trip of the loop
-// adds one table entry in every lane that still has a digit, whatever entry and window it belongs to, so lanes
-// do not wait for each other's zero digits.  Lane k < 32 also starts from window k of the blinding scalar.  The 64
-// partial sums are added by a shuffle tree.  The additions skip every reduction: the running sum's coordinates stay
-// below 6q; the table entries are affine and below q, so an addition in the loop has eleven products.
-template <typename INT>
+constexpr uint32_t CK_QUEUE = 1024;   // ring of digits waiting for a lane: at most 63 left over + 64 x 8 new ones
+
+// One wave per row: sums[row] = rho_row H + sum_c x[row, c] G_c (projective).  The wave reads 64 entries at a time and
+// puts their non-zero WB-bit digits (digit, window, sign, column: one word) on a ring in LDS, window by window with
+// a ballot and a prefix count; whenever 64 digits wait, every lane takes one and adds its table entry.  Lanes
+// therefore never wait for each other's zero digits or shorter entries: a row of n digits costs ceil(n / 64)
+// additions per lane.  Lane k < 32 also starts from window k of the blinding scalar.  The 64 partial sums are added
+// by a shuffle tree.  The additions skip every reduction: the running sum's coordinates stay below 6q; the table
+// entries are affine and below q, so an addition in the loop has eleven products.
+template <typename INT, int WB>
 __global__ __launch_bounds__(64) void k_commit_rows(const INT* x, uint64_t cols, int windows, const G1A* table,
                                                     const uint32_t* rho_le, const G1A* h_table, G1* sums) {
     static_assert(CK_H_WINDOWS <= 64 && CK_WBITS == 8, "one lane per window (byte) of the blinding scalar");
+    constexpr uint32_t DIGITS = (1u << WB) - 1;   // entries per window of the tensor entries' table
+    static_assert(WB <= 12, "a queued digit has 12 bits");
+    __shared__ uint32_t queue[CK_QUEUE];
     const uint64_t row = blockIdx.x;
     const int lane = threadIdx.x;
     G1 acc = g1_identity();
@@ -197,44 +207,46 @@ __global__ __launch_bounds__(64) void k_commit_rows(const INT* x, uint64_t cols,
             acc.Z = fq_one();
         }
     }
-    const INT* xr = x + row * cols;
-    uint64_t c = (uint64_t)lane, mag = 0;
-    bool negative = false, loaded = false;
-    int k = 0;
-    for (;;) {
-        bool active = false;
-        while (c < cols) {   // this lane's next non-zero digit
-            if (!loaded) {
-                const INT s = xr[c];
-                negative = s < 0;
-                mag = negative ? (uint64_t)0 - (uint64_t)(int64_t)s : (uint64_t)s;
-                k = 0;
-                loaded = true;
-            }
-            if (mag == 0) {
-                loaded = false;
-                c += 64;
-                continue;
-            }
-            const int skip = (__ffsll((unsigned long long)mag) - 1) / CK_WBITS;
-            mag >>= CK_WBITS * skip;
-            k += skip;
-            active = true;
-            break;
-        }
-        if (__ballot(active) == 0) break;   // no lane has a digit left
-        if (active) {
-            const uint32_t d = (uint32_t)mag & (uint32_t)CK_DIGITS;
-            const G1A e = table[(c * (uint64_t)windows + (uint64_t)k) * CK_DIGITS + d - 1];
-            const Fq yn = fq_sub2_lazy<2, 1>(fq_zero(), e.y, fq_zero());   // 2q - y: x = r - |x| as a field element is -|x| G
-            Fq y2;
+    // one queued digit: acc += (-1)^sign d 2^(WB k) G_c
+    auto add_item = [&](uint32_t item) {
+        const uint32_t d = item & 0xfffu, k = (item >> 12) & 7u, c = item >> 16;
+        const bool negative = (item >> 15) & 1u;
+        const G1A e = table[((uint64_t)c * (uint64_t)windows + k) * DIGITS + d - 1];
+        const Fq yn = fq_sub2_lazy<2, 1>(fq_zero(), e.y, fq_zero());   // 2q - y: x = r - |x| as a field element is -|x| G
+        Fq y2;
 #pragma unroll
-            for (int i = 0; i < fqc::L; ++i) y2.v[i] = negative ? yn.v[i] : e.y.v[i];
-            acc = g1_add_mixed_lazy_ni(acc, e.x, y2);
-            mag >>= CK_WBITS;
-            ++k;
+        for (int i = 0; i < fqc::L; ++i) y2.v[i] = negative ? yn.v[i] : e.y.v[i];
+        acc = g1_add_mixed_lazy_ni(acc, e.x, y2);
+    };
+    const INT* xr = x + row * cols;
+    const uint64_t below = ((uint64_t)1 << lane) - 1;   // the lanes before this one
+    uint32_t head = 0, tail = 0;                        // the same in every lane
+    for (uint64_t c0 = 0; c0 < cols; c0 += 64) {
+        const uint64_t c = c0 + (uint64_t)lane;         // below 2^15
+        uint64_t mag = 0;
+        uint32_t sign = 0;
+        if (c < cols) {
+            const INT s = xr[c];
+            sign = s < 0 ? 1u : 0u;
+            mag = sign ? (uint64_t)0 - (uint64_t)(int64_t)s : (uint64_t)s;
+        }
+        for (int k = 0; k < windows; ++k) {
+            if (__ballot(mag != 0) == 0) break;
+            const uint32_t d = (uint32_t)mag & DIGITS;
+            mag >>= WB;
+            const uint64_t has = __ballot(d != 0);
+            if (d) queue[(tail + (uint32_t)__popcll(has & below)) % CK_QUEUE] = d | ((uint32_t)k << 12) | (sign << 15) | ((uint32_t)c << 16);
+            tail += (uint32_t)__popcll(has);
+        }
+        __syncthreads();   // one wave: orders the ring's writes before its reads
+#pragma unroll 1
+        while (tail - head >= 64) {
+            add_item(queue[(head + (uint32_t)lane) % CK_QUEUE]);
+            head += 64;
         }
     }
+    __syncthreads();
+    if ((uint32_t)lane < tail - head) add_item(queue[(head + (uint32_t)lane) % CK_QUEUE]);
 #pragma unroll 1
     for (int off = 32; off >= 1; off >>= 1) acc = g1_add_lazy_ni(acc, g1_shfl_down(acc, off));
     if (lane == 0) sums[row] = acc;   // coordinates below 6q
@@ -470,9 +482,11 @@ __global__ __launch_bounds__(64) void k_ck_export(const G1* gens, uint64_t first
 
 struct zkdl_commit_key {
     uint64_t ncols;
-    int windows;      // 8-bit windows of a tensor entry: 4 (32-bit) or 8 (64-bit)
+    int max_bits;     // widest tensor entry served: 32 or 64
+    int wbits;        // bits per window of a tensor entry: 8 or 12
+    int windows;      // windows of a tensor entry: max_bits / wbits, rounded up
     G1* gens;         // device: ncols generators, then H
-    G1A* table;       // device: [ncols][windows][255], affine
+    G1A* table;       // device: [ncols][windows][2^wbits - 1], affine
     G1A* h_table;     // device: [32][255]
 };
 
@@ -581,9 +595,16 @@ extern "C" int zkdl_commit_key_create(zkdl_ctx* ctx, const char* label, uint64_t
     zkdl_commit_key* key = new (std::nothrow) zkdl_commit_key();
     if (!key) return ZKDL_ENOMEM;
     key->ncols = ncols;
-    key->windows = max_bits / CK_WBITS;
+    key->max_bits = max_bits;
+    // wide windows save additions (a 32-bit entry has three 12-bit digits instead of four bytes, a 12-bit one a single
+    // digit) and cost 16 times the entries per window: taken while the tables stay a small part of the memory
+    const uint64_t wide_bytes = sizeof(G1A) * ncols * (uint64_t)((max_bits + CK_WIDE_WBITS - 1) / CK_WIDE_WBITS) *
+                                (((uint64_t)1 << CK_WIDE_WBITS) - 1);
+    key->wbits = ctx->commit_wbits ? ctx->commit_wbits : (wide_bytes <= CK_WIDE_MAX_BYTES ? CK_WIDE_WBITS : CK_WBITS);
+    key->windows = (max_bits + key->wbits - 1) / key->wbits;
+    const uint64_t digits = ((uint64_t)1 << key->wbits) - 1;
     key->gens = (G1*)zk_alloc(ctx, sizeof(G1) * (ncols + 1));
-    key->table = (G1A*)zk_alloc(ctx, sizeof(G1A) * ncols * key->windows * CK_DIGITS);
+    key->table = (G1A*)zk_alloc(ctx, sizeof(G1A) * ncols * key->windows * digits);
     key->h_table = (G1A*)zk_alloc(ctx, sizeof(G1A) * CK_H_WINDOWS * CK_DIGITS);
     if (!key->gens || !key->table || !key->h_table) {
         zkdl_commit_key_destroy(ctx, key);
@@ -596,12 +617,13 @@ extern "C" int zkdl_commit_key_create(zkdl_ctx* ctx, const char* label, uint64_t
     const Fq r2x = r2x_const();
     hipLaunchKernelGGL(k_ck_generators, dim3((unsigned)((ncols + 1 + 63) / 64)), dim3(64), 0, ctx->stream, la, ncols,
                        key->gens, r2x);
-    constexpr uint64_t chunks = (CK_DIGITS + 1) / CK_CHUNK;   // threads per (generator, window)
-    const uint64_t nt = ncols * key->windows * chunks, nh = (uint64_t)CK_H_WINDOWS * chunks;
+    // threads per (generator, window): a 16th of the entries
+    const uint64_t nt = ncols * key->windows * ((digits + 1) / CK_CHUNK);
+    const uint64_t nh = (uint64_t)CK_H_WINDOWS * ((CK_DIGITS + 1) / CK_CHUNK);
     hipLaunchKernelGGL(k_ck_tables, dim3((unsigned)((nt + 63) / 64)), dim3(64), 0, ctx->stream, key->gens, ncols,
-                       key->windows, key->table);
+                       key->windows, key->wbits, key->table);
     hipLaunchKernelGGL(k_ck_tables, dim3((unsigned)((nh + 63) / 64)), dim3(64), 0, ctx->stream, key->gens + ncols,
-                       (uint64_t)1, CK_H_WINDOWS, key->h_table);
+                       (uint64_t)1, CK_H_WINDOWS, CK_WBITS, key->h_table);
     hipError_t e = hipStreamSynchronize(ctx->stream);
     if (e == hipSuccess) e = hipGetLastError();
     if (e != hipSuccess) {
@@ -630,7 +652,7 @@ extern "C" int hyrax_commit(zkdl_ctx* ctx, const zkdl_commit_key* key, const zkd
                             uint8_t* commitments_out, size_t* ncommit) {
     if (!ctx || !key || !X || !commitments_out || !ncommit) return ZKDL_EINVAL;
     if (X->kind != TK_I32 && X->kind != TK_I64) return ZKDL_EINVAL;
-    if (X->kind == TK_I64 && key->windows < 64 / CK_WBITS) return ZKDL_EINVAL;
+    if (X->kind == TK_I64 && key->max_bits < 64) return ZKDL_EINVAL;
     int m = 0;
     while (((uint64_t)1 << m) < X->numel) ++m;
     if (((uint64_t)1 << m) != X->numel) return ZKDL_EINVAL;
@@ -658,11 +680,18 @@ extern "C" int hyrax_commit(zkdl_ctx* ctx, const zkdl_commit_key* key, const zkd
     if (rc == ZKDL_OK && blind) e = hipMemcpyAsync(rho_dev, blind, rows * 32, hipMemcpyHostToDevice, ctx->stream);
     if (rc == ZKDL_OK && e == hipSuccess) {
         // the key's tables have `windows` entries per generator whatever the tensor's width
-        if (X->kind == TK_I32)
-            hipLaunchKernelGGL((k_commit_rows<int32_t>), dim3((unsigned)rows), dim3(64), 0, ctx->stream,
+        const dim3 grid((unsigned)rows), block(64);
+        if (X->kind == TK_I32 && key->wbits == CK_WIDE_WBITS)
+            hipLaunchKernelGGL((k_commit_rows<int32_t, CK_WIDE_WBITS>), grid, block, 0, ctx->stream,
                                (const int32_t*)X->data, cols, key->windows, key->table, rho_dev, key->h_table, part);
+        else if (X->kind == TK_I32)
+            hipLaunchKernelGGL((k_commit_rows<int32_t, CK_WBITS>), grid, block, 0, ctx->stream,
+                               (const int32_t*)X->data, cols, key->windows, key->table, rho_dev, key->h_table, part);
+        else if (key->wbits == CK_WIDE_WBITS)
+            hipLaunchKernelGGL((k_commit_rows<int64_t, CK_WIDE_WBITS>), grid, block, 0, ctx->stream,
+                               (const int64_t*)X->data, cols, key->windows, key->table, rho_dev, key->h_table, part);
         else
-            hipLaunchKernelGGL((k_commit_rows<int64_t>), dim3((unsigned)rows), dim3(64), 0, ctx->stream,
+            hipLaunchKernelGGL((k_commit_rows<int64_t, CK_WBITS>), grid, block, 0, ctx->stream,
                                (const int64_t*)X->data, cols, key->windows, key->table, rho_dev, key->h_table, part);
         hipLaunchKernelGGL(k_commit_affine, dim3((unsigned)((rows + 63) / 64)), dim3(64), 0, ctx->stream, part, rows, out_dev);
         e = hipMemcpyAsync(commitments_out, out_dev, rows * 96, hipMemcpyDeviceToHost, ctx->stream);

@@ -82,6 +82,8 @@ struct zkdl_ctx {
     uint32_t pend_len;
     // zkReLU: the columns of a round are cut into chunks until this many threads are busy
     uint64_t zk_fill_threads;
+    // commitment keys: bits per window of a tensor entry's table (0: chosen by table size; 8 or 12)
+    int commit_wbits;
     // optional per-kernel-class timing with HIP events on the context's stream
     bool prof_on;
     struct ProfSpan {

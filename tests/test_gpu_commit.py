@@ -27,19 +27,26 @@ def test_generators_match_the_oracle(lib, ctx):
 
 @pytest.mark.parametrize("numel,dtype,blinded", [(1, "i32", True), (2, "i32", False), (64, "i32", True), (256, "i64", True),
                                                  (2048, "i32", True), (512, "i64", False)])
-def test_row_commitments_match_the_oracle(lib, ctx, numel, dtype, blinded):
+@pytest.mark.parametrize("wbits", [8, 12])
+def test_row_commitments_match_the_oracle(lib, ctx, numel, dtype, blinded, wbits):
+    """Both widths of the fixed-base windows (the key picks one by table size; the commitments do not depend on it)."""
     import torch
-    say(f"hyrax_commit numel={numel} {dtype} blinded={blinded}")
+    say(f"hyrax_commit numel={numel} {dtype} blinded={blinded} window bits={wbits}")
     rng = np.random.default_rng(numel + 7)
     if dtype == "i32":
         vals = rng.integers(-2 ** 31, 2 ** 31, numel, dtype=np.int64).astype(np.int32)
-        edge = [0, -1, 2 ** 31 - 1, -2 ** 31, 1, 16, -16, 255]
+        edge = [0, -1, 2 ** 31 - 1, -2 ** 31, 1, 16, -16, 255, 4095, 4096, -4096, 2 ** 24 - 1, -2 ** 24, 256, 0xFFF000]
     else:
         vals = rng.integers(-2 ** 47, 2 ** 47, numel, dtype=np.int64)
-        edge = [0, -1, 2 ** 63 - 1, -2 ** 63, 2 ** 47 - 1, -2 ** 47, 1 << 60, -(1 << 32)]
+        edge = [0, -1, 2 ** 63 - 1, -2 ** 63, 2 ** 47 - 1, -2 ** 47, 1 << 60, -(1 << 32), 4095, -4096, 1 << 36,
+                (1 << 48) - 1, 0xFFF000FFF000]
     vals[:min(numel, len(edge))] = edge[:min(numel, len(edge))]
     rows, cols = EC.matrix_shape(numel)
-    key = lib.CommitKey(ctx, b"rows", cols, 64 if dtype == "i64" else 32)
+    ctx.set_commit_window_bits(wbits)
+    try:
+        key = lib.CommitKey(ctx, b"rows", cols, 64 if dtype == "i64" else 32)
+    finally:
+        ctx.set_commit_window_bits(0)
     blind = [int(v) for v in rng.integers(1, 2 ** 62, rows)] if blinded else None
     if blinded:
         blind[0] = R_MOD - 1
@@ -220,6 +227,8 @@ def test_commit_rejects_bad_arguments(lib, ctx):
         lib.CommitKey(ctx, b"x" * 17, 4)
     with pytest.raises(lib.ZkdlError):
         lib.CommitKey(ctx, b"x", 3)
+    with pytest.raises(lib.ZkdlError):
+        ctx.set_commit_window_bits(10)
 
 
 def test_full_size_activation_stack_opens_correctly(lib, ctx):
