@@ -15,6 +15,9 @@ laid out as a matrix.  Readings where it is silent:
    (x, y) with the smaller of the two roots y, multiplied by the cofactor to land in the subgroup (a
    candidate that becomes the identity is skipped).  tag = b"zkdl-mi355x/g1/" + label; the blinding
    generator H is index 0xFFFFFFFF of the same label.  Nobody knows a discrete-log relation between them;
+ * the verifier of an opening checks that every row commitment it is given lies in that subgroup, r C = O: Sec. 2.3
+   states the scheme and its homomorphism for a group of prime order, and the curve's group is larger than the
+   subgroup (cofactor 0x396C8C00..AAAB), so a point on the curve is not yet an element of the group;
  * layout: a tensor of 2^m entries is a matrix of R = 2^ceil(m/2) rows and C = 2^floor(m/2) columns, row
    index = the leading variables; row j is committed with the C generators and its own blinding rho_j;
  * proof of evaluation at (v_row, v_col): the prover sends T = sum_j beta~(v_row, j) S[j, :] and
@@ -76,6 +79,11 @@ def mul(k, p):
         p = add(p, p)
         k >>= 1
     return acc
+
+
+def in_subgroup(p):
+    """Membership in the group of prime order r that Sec. 2.3 works in: on the curve and r p = O."""
+    return on_curve(p) and mul(R_MOD, p) is INF
 
 
 def generator(label, index):
@@ -140,6 +148,7 @@ def verify_opening(commitments, point, t, rho_star, y, gens, h):
     lr = ilog2(rows)
     assert len(point) == lr + ilog2(cols)
     b_row, b_col = beta_table(point[:lr]), beta_table(point[lr:])
+    assert all(in_subgroup(c) for c in commitments), "a commitment is not an element of the group of order r"
     c_star = INF
     for j in range(rows):
         c_star = add(c_star, mul(int(b_row[j]), commitments[j]))

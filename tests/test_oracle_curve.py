@@ -92,3 +92,43 @@ def test_row_commitments_open_to_the_multilinear_extension(numel):
         other[-1] += 1
         with pytest.raises(AssertionError):
             EC.verify_opening(EC.commit_rows(other, rhos, gens, h), point, t, rho_star, y, gens, h)
+
+
+def _point_outside_the_subgroup(seed):
+    """A point of the curve found by trying x = seed, seed + 1, ..: the curve has h r points, so one found this way
+    lies in the subgroup of order r with probability 1 / h."""
+    x = seed
+    while True:
+        rhs = (x * x * x + EC.CURVE_B) % EC.Q_MOD
+        y = pow(rhs, (EC.Q_MOD + 1) // 4, EC.Q_MOD)
+        if y * y % EC.Q_MOD == rhs and not EC.mul(R_MOD, (x, y)) is EC.INF:
+            return (x, y)
+        x += 1
+
+
+def test_subgroup_membership_is_more_than_being_on_the_curve():
+    """Sec. 2.3 works in a group of prime order: a verifier must not take a point of the curve for an element of it."""
+    assert EC.in_subgroup(G1) and EC.in_subgroup(EC.INF) and EC.in_subgroup(EC.mul(987654321, G1))
+    three_torsion = (0, 2)                                       # 2^2 = 0^3 + 4; a point with x = 0 has order 3
+    assert EC.on_curve(three_torsion) and EC.mul(3, three_torsion) is EC.INF
+    assert not EC.in_subgroup(three_torsion)
+    p = _point_outside_the_subgroup(5)
+    assert EC.on_curve(p) and not EC.in_subgroup(p)
+    assert EC.in_subgroup(EC.mul(EC.COFACTOR, p))                # the cofactor takes it into the subgroup
+    assert not EC.in_subgroup(EC.add(G1, three_torsion))         # a subgroup point moved by a torsion point
+    assert not EC.in_subgroup((G1_X, G1_Y + 1))                  # not on the curve at all
+
+
+def test_opening_is_refused_when_a_commitment_leaves_the_subgroup():
+    rng = np.random.default_rng(5)
+    vals = [int(v) for v in rng.integers(-100, 100, 16)]
+    gens, h = EC.generators(b"sub", 4)
+    rhos = [int(v) for v in rng.integers(1, 2 ** 60, 4)]
+    coms = EC.commit_rows(vals, rhos, gens, h)
+    point = [int(v) for v in rng.integers(1, 2 ** 60, 4)]
+    t, rho_star, y = EC.open_rows(vals, rhos, point)
+    assert EC.verify_opening(coms, point, t, rho_star, y, gens, h)
+    # the same commitment moved by a point of order 3: still on the curve, no longer in the group
+    moved = [EC.add(coms[0], (0, 2))] + coms[1:]
+    with pytest.raises(AssertionError, match="group of order r"):
+        EC.verify_opening(moved, point, t, rho_star, y, gens, h)
