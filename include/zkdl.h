@@ -519,15 +519,18 @@ int hyrax_open(zkdl_ctx* ctx, const zkdl_tensor* X, const zkdl_fr* blind, const 
  * proof-of-evaluation line): C* = sum_j beta~(v_row, j) C_j over the nrows row commitments (host, 96 bytes
  * each), Commit(T; rho*) on the key's generators, and <T, beta~(v_col, .)> against y.  point: npoint = log2 nrows
  * + log2 C canonical elements, row coordinates first; T: C elements; rho: rho* or NULL for zero blinding.
- * *verdict = 0 accepted, 1 malformed input (an element not below r, a commitment not on the curve), 2 the opened
- * row does not match the combined commitment, 3 wrong evaluation.  combined_out (may be NULL): C* as 96 bytes.
- * Both sums run on the GPU, eight lanes per term (4-bit windows over the 255-bit scalar, every point operation
- * shared by the eight), the weights and the inner product on the host. */
+ * *verdict = 0 accepted, 1 malformed input (an element not below r, a commitment that is not an element of the
+ * group of order r Sec. 2.3 works in: off the curve, or on it but outside the subgroup), 2 the opened row does not
+ * match the combined commitment, 3 wrong evaluation.  combined_out (may be NULL): C* as 96 bytes.
+ * Both sums run on the GPU, eight lanes per term (every point operation shared by the eight; a scalar split in
+ * two halves of 128 bits by the curve's endomorphism, 4-bit windows), next to the membership test of the
+ * commitments; the weights, the split and the inner product on the host. */
 int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uint8_t* commitments, size_t nrows,
                  const zkdl_fr* point, size_t npoint, const zkdl_fr* T, const zkdl_fr* rho, const zkdl_fr* y,
                  int* verdict, uint8_t* combined_out);
 
-/* Re-derives the constants of the base-field arithmetic on the host; ZKDL_OK if they match. */
+/* Re-derives the constants of the base-field arithmetic on the host and checks the unreduced point additions, the
+ * endomorphism's constant and the split of a scalar against plain computations; ZKDL_OK if they match. */
 int zkdl_commit_selfcheck(void);
 
 /* ---- per-kernel timing (for callers that measure; paper-independent) -------

@@ -390,18 +390,55 @@ __device__ inline G1 g1_canonical(const G1& p) {   // coordinates below 2q -> be
 constexpr int MSM_TERMS = 64 / COOP;   // terms per block
 constexpr int G1_WORDS = 3 * fqc::L;
 
+// |z| for the curve's parameter z = -0xd201000000010000: r = z^4 - z^2 + 1 = (-z^2)^2 + (-z^2) + 1, so -z^2 is a
+// cube root of unity modulo r.  The map phi(x, y) = (beta x, y), beta a cube root of unity in F_q, is an
+// endomorphism of the curve; on the subgroup of order r it is multiplication by a cube root of unity modulo r, and
+// beta is chosen (on the host, by trying both roots on a subgroup point: endo_beta) so that phi(P) = -z^2 P there.
+constexpr uint64_t CK_Z_ABS = 0xd201000000010000ull;
+
+// |z| p for a group of eight lanes: the top bit of |z| is bit 63
+__device__ inline G1 coop_mul_zabs(const G1& p, int j) {
+    G1 acc = p;
+#pragma unroll 1
+    for (int bit = 62; bit >= 0; --bit) {
+        acc = g1_coop<1>(acc, acc, j);
+        if ((CK_Z_ABS >> bit) & 1ull) acc = g1_coop<0>(acc, p, j);   // the same branch in every lane
+    }
+    return acc;
+}
+
 // Eight lanes per term of two sums in one launch: the blocks below nb_bytes take the points given as affine bytes
-// (term t = 8 block + group < n_bytes, scalar scal[t]), the others the key's generators (term t' = 8 (block -
-// nb_bytes) + group < n_g1, scalar scal[n_bytes + t']).  Scalars: 8 words, canonical, little-endian.  A group first
-// builds the 15 multiples of its point (in LDS), then runs over the 64 4-bit windows from the top: four doublings
-// and one addition of a table entry (of the identity for a zero digit: the formulas are complete, and the wave
-// stays in step).  Three more additions sum the block's terms: part[block], coordinates below 2q.
-// bad[0] is set if a point given as bytes is malformed.
+// (term t = 8 block + group < n_bytes, scalar scal[t]), the next nb_g1 blocks the key's generators (term t' = 8
+// (block - nb_bytes) + group < n_g1, scalar scal[n_bytes + t']).  A scalar k < r comes split as k = a + b z^2 with
+// a, b < 2^128 (4 + 4 words, little-endian), so that k P = a P + b (-phi(P)) for P in the subgroup: half as many
+// doublings.  A group first builds the 15 multiples of its point and their images (beta X, -Y, Z) in LDS, then runs
+// over the 32 4-bit windows from the top: four doublings and two additions of table entries (of the identity for a
+// zero digit: the formulas are complete, and the wave stays in step).  Three more additions sum the block's terms:
+// part[block], coordinates below 2q.
+// The last nb_bytes blocks check that the points given as bytes are elements of the subgroup, for which the split
+// holds and in which Sec. 2.3 works: phi(P) = -z^2 P exactly when r P = O (if phi(P) = -z^2 P then
+// (z^4 - z^2 + 1) P = (phi^2 + phi + 1) P = O; conversely phi acts on the subgroup as the root -z^2 by the choice
+// of beta), at the cost of 126 doublings and 10 additions next to the sums' 128 doublings.
+// bad[0] is set if a point given as bytes is malformed or outside the subgroup.
 __global__ __launch_bounds__(64) void k_msm_terms(const uint8_t* pts_bytes, uint64_t n_bytes, unsigned nb_bytes,
-                                                  const G1* pts_g1, uint64_t n_g1, const uint32_t* scal, G1* part,
-                                                  uint32_t* bad) {
-    __shared__ uint32_t tab[MSM_TERMS][15][G1_WORDS];
+                                                  const G1* pts_g1, uint64_t n_g1, unsigned nb_g1, const uint32_t* scal,
+                                                  G1* part, uint32_t* bad, Fq beta) {
+    __shared__ uint32_t tab[2][MSM_TERMS][15][G1_WORDS];
     const int j = threadIdx.x % COOP, grp = threadIdx.x / COOP;
+    if (blockIdx.x >= nb_bytes + nb_g1) {   // subgroup check of eight of the points given as bytes
+        const uint64_t t = (blockIdx.x - nb_bytes - nb_g1) * (uint64_t)MSM_TERMS + grp;
+        const bool live = t < n_bytes;
+        bool ok = true;
+        const G1 p = live ? g1_from_bytes(pts_bytes + 96 * t, &ok) : g1_identity();
+        const G1 zz = coop_mul_zabs(coop_mul_zabs(p, j), j);   // z^2 P
+        if (live && j == 0 && !fq_is_zero(p.Z)) {              // P affine: beta x Z' = X' and y Z' = -Y'
+            const Fq zc = fq_cond_sub(zz.Z);
+            ok = ok && fq_eq(fq_mul_ni(fq_mul_ni(beta, p.X), zc), fq_cond_sub(zz.X));
+            ok = ok && fq_is_zero(fq_add(fq_mul_ni(p.Y, zc), fq_cond_sub(zz.Y)));
+            if (!ok) bad[0] = 1;
+        }
+        return;
+    }
     const bool from_bytes = blockIdx.x < nb_bytes;
     const uint64_t t = (from_bytes ? blockIdx.x : blockIdx.x - nb_bytes) * (uint64_t)MSM_TERMS + grp;
     const bool live = t < (from_bytes ? n_bytes : n_g1);
@@ -419,35 +456,43 @@ __global__ __launch_bounds__(64) void k_msm_terms(const uint8_t* pts_bytes, uint
     }
     G1 acc = base;
 #pragma unroll 1
-    for (int d = 0; d < 15; ++d) {   // tab[d] = (d + 1) base
+    for (int d = 0; d < 15; ++d) {   // tab[0][d] = (d + 1) base, tab[1][d] = -phi of it
         if (d) acc = g1_coop<0>(acc, base, j);
+        const Fq bx = fq_mul_ni(acc.X, beta);
+        const Fq ny = fq_neg(fq_cond_sub(acc.Y));
         if (j == 0) {
 #pragma unroll
             for (int i = 0; i < fqc::L; ++i) {
-                tab[grp][d][i] = acc.X.v[i];
-                tab[grp][d][fqc::L + i] = acc.Y.v[i];
-                tab[grp][d][2 * fqc::L + i] = acc.Z.v[i];
+                tab[0][grp][d][i] = acc.X.v[i];
+                tab[0][grp][d][fqc::L + i] = acc.Y.v[i];
+                tab[0][grp][d][2 * fqc::L + i] = acc.Z.v[i];
+                tab[1][grp][d][i] = bx.v[i];
+                tab[1][grp][d][fqc::L + i] = ny.v[i];
+                tab[1][grp][d][2 * fqc::L + i] = acc.Z.v[i];
             }
         }
     }
     __syncthreads();
     acc = g1_identity();
 #pragma unroll 1
-    for (int win = 63; win >= 0; --win) {
+    for (int win = 31; win >= 0; --win) {
 #pragma unroll 1
         for (int q = 0; q < 4; ++q) acc = g1_coop<1>(acc, acc, j);
-        const uint32_t dg = (k[win >> 3] >> (4 * (win & 7))) & 15u;
-        G1 e = g1_identity();
-        if (dg) {
-            const uint32_t* src = tab[grp][dg - 1];
+#pragma unroll 1
+        for (int half = 0; half < 2; ++half) {
+            const uint32_t dg = (k[4 * half + (win >> 3)] >> (4 * (win & 7))) & 15u;
+            G1 e = g1_identity();
+            if (dg) {
+                const uint32_t* src = tab[half][grp][dg - 1];
 #pragma unroll
-            for (int i = 0; i < fqc::L; ++i) {
-                e.X.v[i] = src[i];
-                e.Y.v[i] = src[fqc::L + i];
-                e.Z.v[i] = src[2 * fqc::L + i];
+                for (int i = 0; i < fqc::L; ++i) {
+                    e.X.v[i] = src[i];
+                    e.Y.v[i] = src[fqc::L + i];
+                    e.Z.v[i] = src[2 * fqc::L + i];
+                }
             }
+            acc = g1_coop<0>(acc, e, j);
         }
-        acc = g1_coop<0>(acc, e, j);
     }
 #pragma unroll 1
     for (int off = 32; off >= COOP; off >>= 1) acc = g1_coop<0>(acc, g1_shfl_down(acc, off), j);
@@ -490,9 +535,129 @@ struct zkdl_commit_key {
     G1A* h_table;     // device: [32][255]
 };
 
+// ---- host: the endomorphism's constant and the split of a scalar -------------------------------------------------
+// a point of the curve found by trying x = 1, 2, .. (Montgomery form, Z = 1)
+static bool host_curve_point(G1* out) {
+    Fq xs = fq_zero();
+    const Fq four = fq_add(fq_add(fq_one(), fq_one()), fq_add(fq_one(), fq_one()));
+    for (int t = 0; t < 64; ++t) {
+        xs = fq_add(xs, fq_one());
+        const Fq rhs = fq_add(fq_mul(fq_sqr(xs), xs), four);
+        const Fq y = fq_pow(rhs, fqc::EXP_SQRT);
+        if (fq_eq(fq_sqr(y), rhs) && !fq_is_zero(y)) {
+            out->X = xs;
+            out->Y = y;
+            out->Z = fq_one();
+            return true;
+        }
+    }
+    return false;
+}
+
+// beta with phi(P) = (beta x, y) = -z^2 P on the subgroup: beta = (-1 +- sqrt(-3)) / 2, the sign found by trying both
+// on a point that the cofactor has taken into the subgroup.  false if neither fits (a broken constant).
+static bool make_endo_beta(Fq* beta) {
+    const Fq one = fq_one(), two = fq_add(one, one), m3 = fq_neg(fq_add(two, one));
+    const Fq s = fq_pow(m3, fqc::EXP_SQRT);
+    if (!fq_eq(fq_sqr(s), m3)) return false;
+    const Fq half = fq_inv_euclid(two);
+    const Fq cand[2] = {fq_mul(fq_sub(s, one), half), fq_mul(fq_sub(fq_neg(s), one), half)};
+    G1 p0;
+    if (!host_curve_point(&p0)) return false;
+    const G1 p = g1_mul_words(p0, fqc::COFACTOR);
+    if (fq_is_zero(p.Z)) return false;
+    const uint32_t zw[2] = {(uint32_t)CK_Z_ABS, (uint32_t)(CK_Z_ABS >> 32)};
+    const G1 q = g1_mul_words(g1_mul_words(p, zw), zw);   // z^2 P
+    for (int c = 0; c < 2; ++c) {
+        const bool x_fits = fq_eq(fq_mul(fq_mul(cand[c], p.X), q.Z), fq_mul(q.X, p.Z));
+        const bool y_fits = fq_is_zero(fq_add(fq_mul(p.Y, q.Z), fq_mul(q.Y, p.Z)));
+        if (x_fits && y_fits && !fq_eq(cand[c], one) && fq_eq(fq_mul(fq_sqr(cand[c]), cand[c]), one)) {
+            *beta = cand[c];
+            return true;
+        }
+    }
+    return false;
+}
+
+static bool endo_beta(Fq* beta) {
+    static Fq value;
+    static const bool ok = make_endo_beta(&value);
+    *beta = value;
+    return ok;
+}
+
+// k = a + b z^2 with a < z^2: out[0..3] = a, out[4..7] = b (32-bit words, least significant first); false unless
+// b < 2^128 (true for every k < r < z^4).  Long division in base 2^32 (Knuth, Algorithm D; the divisor's top bit
+// is set, so nothing is shifted), and the result is multiplied out again before it is trusted.
+static bool glv_split(const uint32_t k[8], uint32_t out[8]) {
+    const unsigned __int128 zz = (unsigned __int128)CK_Z_ABS * CK_Z_ABS;
+    uint32_t v[4], un[9], q[5];
+    for (int i = 0; i < 4; ++i) v[i] = (uint32_t)(zz >> (32 * i));
+    for (int i = 0; i < 8; ++i) un[i] = k[i];
+    un[8] = 0;
+    for (int jj = 4; jj >= 0; --jj) {
+        const uint64_t num = ((uint64_t)un[jj + 4] << 32) | un[jj + 3];
+        uint64_t qhat = num / v[3], rhat = num % v[3];
+        while (qhat >> 32 || qhat * v[2] > ((rhat << 32) | un[jj + 2])) {
+            --qhat;
+            rhat += v[3];
+            if (rhat >> 32) break;
+        }
+        uint64_t carry = 0;
+        int64_t borrow = 0;
+        for (int i = 0; i < 4; ++i) {
+            const uint64_t prod = qhat * v[i] + carry;
+            carry = prod >> 32;
+            const int64_t d = (int64_t)un[jj + i] - (int64_t)(uint32_t)prod - borrow;
+            un[jj + i] = (uint32_t)d;
+            borrow = d < 0 ? 1 : 0;
+        }
+        const int64_t d = (int64_t)un[jj + 4] - (int64_t)carry - borrow;
+        un[jj + 4] = (uint32_t)d;
+        if (d < 0) {   // the estimate was one too large: add the divisor back
+            --qhat;
+            uint64_t c = 0;
+            for (int i = 0; i < 4; ++i) {
+                c += (uint64_t)un[jj + i] + v[i];
+                un[jj + i] = (uint32_t)c;
+                c >>= 32;
+            }
+            un[jj + 4] += (uint32_t)c;
+        }
+        q[jj] = (uint32_t)qhat;
+    }
+    if (q[4] != 0) return false;
+    unsigned __int128 a = 0, b = 0;
+    for (int i = 3; i >= 0; --i) {
+        a = (a << 32) | un[i];
+        b = (b << 32) | q[i];
+        out[i] = un[i];
+        out[4 + i] = q[i];
+    }
+    if (a >= zz || un[4] || un[5] || un[6] || un[7]) return false;
+    // a + b z^2 = k, multiplied out in 32-bit words
+    uint32_t back[9] = {0};
+    for (int i = 0; i < 4; ++i) {
+        uint64_t c = 0;
+        for (int l = 0; l < 4; ++l) {
+            c += (uint64_t)q[i] * v[l] + back[i + l];
+            back[i + l] = (uint32_t)c;
+            c >>= 32;
+        }
+        back[i + 4] += (uint32_t)c;
+    }
+    uint64_t c = 0;
+    for (int i = 0; i < 8; ++i) {
+        c += (uint64_t)back[i] + (i < 4 ? un[i] : 0u);
+        if ((uint32_t)c != k[i]) return false;
+        c >>= 32;
+    }
+    return c == 0;
+}
+
 // host-side check of the constants of fq.cuh (no GPU needed): Montgomery one and R^2 by repeated doubling,
 // the Montgomery factor, the square-root and inversion exponents
-extern "C" int zkdl_commit_selfcheck(void) {
+static int commit_selfcheck_run() {
     Fq x = fq_zero();
     x.v[0] = 1;
     for (int i = 0; i < 406; ++i) x = fq_add(x, x);
@@ -522,20 +687,8 @@ extern "C" int zkdl_commit_selfcheck(void) {
     // the additions without reductions against the reduced one, on multiples of a point found by trying x = 1, 2, ..:
     // a running sum that only ever goes through the lazy forms (so its coordinates take the bounds the kernel's do),
     // the sum from the identity, a point added to itself and to its negative
-    G1 base = g1_identity();
-    Fq xs = fq_zero();
-    const Fq four = fq_add(fq_add(fq_one(), fq_one()), fq_add(fq_one(), fq_one()));
-    for (int t = 0; t < 64 && fq_is_zero(base.Z); ++t) {
-        xs = fq_add(xs, fq_one());
-        const Fq rhs = fq_add(fq_mul(fq_sqr(xs), xs), four);
-        const Fq y = fq_pow(rhs, fqc::EXP_SQRT);
-        if (fq_eq(fq_sqr(y), rhs) && !fq_is_zero(y)) {
-            base.X = xs;
-            base.Y = y;
-            base.Z = fq_one();
-        }
-    }
-    if (fq_is_zero(base.Z)) return ZKDL_EINVAL;
+    G1 base;
+    if (!host_curve_point(&base)) return ZKDL_EINVAL;
     auto same = [](const G1& a, const G1& b) {   // equal as projective points, coordinates reduced
         return fq_eq(fq_mul(a.X, b.Z), fq_mul(b.X, a.Z)) && fq_eq(fq_mul(a.Y, b.Z), fq_mul(b.Y, a.Z)) &&
                fq_is_zero(a.Z) == fq_is_zero(b.Z);
@@ -572,7 +725,56 @@ extern "C" int zkdl_commit_selfcheck(void) {
         const G1 o2 = g1_reduce(g1_add_lazy_with(base, g1_neg(base), lazy));
         if (!fq_is_zero(o2.Z) || !fq_is_zero(o2.X)) return ZKDL_EINVAL;
     }
+    // the endomorphism: its constant, and the split of a scalar on edge values (0, 1, z^2 - 1, z^2, z^2 + 1, r - 1,
+    // 2^256 - 1 is refused) and on a chain of mixed words; with the split, k P = a P + b (-phi(P)) on a subgroup point
+    Fq beta;
+    if (!endo_beta(&beta)) return ZKDL_EINVAL;
+    {
+        const unsigned __int128 zz = (unsigned __int128)CK_Z_ABS * CK_Z_ABS;
+        uint32_t ks[8][8] = {};
+        ks[1][0] = 1;
+        for (int i = 0; i < 4; ++i) {
+            ks[2][i] = (uint32_t)((zz - 1) >> (32 * i));
+            ks[3][i] = (uint32_t)(zz >> (32 * i));
+            ks[4][i] = (uint32_t)((zz + 1) >> (32 * i));
+        }
+        for (int i = 0; i < 8; ++i) ks[5][i] = frc::MOD[i];
+        ks[5][0] -= 1;
+        uint32_t w = 0x9e3779b9u;
+        for (int i = 0; i < 8; ++i) {
+            w = w * 1664525u + 1013904223u;
+            ks[6][i] = i == 7 ? (w & 0x3fffffffu) : w;
+            ks[7][i] = i == 7 ? 0x73eda752u : ~w;
+        }
+        const G1 p = g1_mul_words(base, fqc::COFACTOR);   // in the subgroup
+        G1 nphi = p;                                      // -phi(P) = (beta X, -Y, Z)
+        nphi.X = fq_mul(p.X, beta);
+        nphi.Y = fq_neg(p.Y);
+        for (int t = 0; t < 8; ++t) {
+            uint32_t ab[8];
+            if (!glv_split(ks[t], ab)) return ZKDL_EINVAL;
+            const uint32_t a4[4] = {ab[0], ab[1], ab[2], ab[3]}, b4[4] = {ab[4], ab[5], ab[6], ab[7]};
+            if (t >= 5 && !same(g1_mul_words(p, ks[t]), g1_add(g1_mul_words(p, a4), g1_mul_words(nphi, b4))))
+                return ZKDL_EINVAL;
+        }
+        uint32_t all_ones[8], ab[8];
+        for (int i = 0; i < 8; ++i) all_ones[i] = 0xffffffffu;
+        if (glv_split(all_ones, ab)) return ZKDL_EINVAL;   // the quotient does not fit 128 bits
+        // a point outside the subgroup does not pass the membership test phi(P) = -z^2 P
+        const uint32_t zw[2] = {(uint32_t)CK_Z_ABS, (uint32_t)(CK_Z_ABS >> 32)};
+        const G1 q = g1_mul_words(g1_mul_words(base, zw), zw);
+        const bool base_in = fq_is_zero(g1_mul_words(base, frc::MOD).Z);
+        const bool passes = fq_eq(fq_mul(fq_mul(beta, base.X), q.Z), fq_mul(q.X, base.Z)) &&
+                            fq_is_zero(fq_add(fq_mul(base.Y, q.Z), fq_mul(q.Y, base.Z)));
+        if (base_in != passes) return ZKDL_EINVAL;
+    }
     return ZKDL_OK;
+}
+
+// the checks run once per process: they take some milliseconds of host arithmetic
+extern "C" int zkdl_commit_selfcheck(void) {
+    static const int rc = commit_selfcheck_run();
+    return rc;
 }
 
 extern "C" int zkdl_commit_key_destroy(zkdl_ctx* ctx, zkdl_commit_key* key) {
@@ -767,22 +969,29 @@ extern "C" int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uin
         Fr t;
         if (!host_fr_from_bytes(T[c], &t)) return ZKDL_OK;
         acc = fr_add(acc, fr_mul(b_col[c], t));
-        memcpy(&scal[8 * (nrows + c)], T[c].le, 32);
+        uint32_t kw[8];
+        memcpy(kw, T[c].le, 32);
+        if (!glv_split(kw, &scal[8 * (nrows + c)])) return ZKDL_EINVAL;
     }
     if (!host_fr_from_bytes(*y, &ym) || (rho && !host_fr_from_bytes(*rho, &rm))) return ZKDL_OK;
     for (size_t j = 0; j < nrows; ++j) {
         const Fr plain = fr_from_mont(b_row[j]);
-        memcpy(&scal[8 * j], plain.v, 32);
+        if (!glv_split(plain.v, &scal[8 * j])) return ZKDL_EINVAL;
     }
-    if (rho) memcpy(&scal[8 * (nrows + cols)], rho->le, 32);
-    else memset(&scal[8 * (nrows + cols)], 0, 32);
+    if (rho) {
+        uint32_t kw[8];
+        memcpy(kw, rho->le, 32);
+        if (!glv_split(kw, &scal[8 * (nrows + cols)])) return ZKDL_EINVAL;
+    }
+    Fq beta;
+    if (!endo_beta(&beta)) return ZKDL_EINVAL;
     ZK_HIP(ctx, hipSetDevice(ctx->device));
     // sum 1: the row commitments with the weights beta~(v_row, .); sum 2: Commit(T; rho*) on the key's generators
     const uint64_t n2 = cols + 1;
     const unsigned g1 = (unsigned)((nrows + MSM_TERMS - 1) / MSM_TERMS), g2 = (unsigned)((n2 + MSM_TERMS - 1) / MSM_TERMS);
     uint8_t* d_comm = (uint8_t*)zk_alloc(ctx, nrows * 96);
     uint32_t* d_scal = (uint32_t*)zk_alloc(ctx, scal.size() * 4);
-    G1* d_part = (G1*)zk_alloc(ctx, sizeof(G1) * (g1 + g2));
+    G1* d_part = (G1*)zk_alloc(ctx, sizeof(G1) * (g1 + g2));   // the blocks that check the subgroup write none
     G1* d_gens = (G1*)zk_alloc(ctx, sizeof(G1) * n2);   // G_0 .. G_{cols-1}, H
     uint8_t* d_out = (uint8_t*)zk_alloc(ctx, 256);
     int rc = (d_comm && d_scal && d_part && d_gens && d_out) ? ZKDL_OK : ZKDL_ENOMEM;
@@ -796,8 +1005,8 @@ extern "C" int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uin
         if (e == hipSuccess)
             e = hipMemcpyAsync(d_gens + cols, key->gens + key->ncols, sizeof(G1), hipMemcpyDeviceToDevice, ctx->stream);
         if (e == hipSuccess) {
-            hipLaunchKernelGGL(k_msm_terms, dim3(g1 + g2), dim3(64), 0, ctx->stream, d_comm, (uint64_t)nrows, g1, d_gens, n2,
-                               d_scal, d_part, d_scal + 8 * (nrows + cols + 1));
+            hipLaunchKernelGGL(k_msm_terms, dim3(g1 + g2 + g1), dim3(64), 0, ctx->stream, d_comm, (uint64_t)nrows, g1, d_gens,
+                               n2, g2, d_scal, d_part, d_scal + 8 * (nrows + cols + 1), beta);
             hipLaunchKernelGGL(k_msm_finish, dim3(2), dim3(64), 0, ctx->stream, d_part, (uint64_t)g1, (uint64_t)g2, d_out);
             e = hipMemcpyAsync(h_out, d_out, 192, hipMemcpyDeviceToHost, ctx->stream);
             if (e == hipSuccess)
@@ -816,7 +1025,7 @@ extern "C" int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uin
     ZK_HIP(ctx, e);
     uint32_t bad;
     memcpy(&bad, h_out + 192, 4);
-    if (bad) return ZKDL_OK;                       // verdict 1: a commitment is not a point of the curve
+    if (bad) return ZKDL_OK;                       // verdict 1: a commitment is not an element of the group
     if (combined_out) memcpy(combined_out, h_out, 96);
     if (memcmp(h_out, h_out + 96, 96) != 0) {
         *verdict = 2;                              // Commit(T; rho*) is not the combined commitment

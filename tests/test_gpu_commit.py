@@ -126,6 +126,8 @@ def test_library_verifies_openings_as_the_oracle_does(lib, ctx, numel, dtype, bl
     if rows > 1:
         both([raw[1], raw[0]] + raw[2:], point, t, rho_in, y, 2)
         both(raw, [(point[0] + 1) % R_MOD] + point[1:], t, rho_in, y, 2)
+    # a commitment moved by a point of order 3 is on the curve but no element of the group of order r
+    both([EC.point_to_bytes(EC.add(coms[0], (0, 2)))] + raw[1:], point, t, rho_in, y, 1)
     # malformed inputs: a commitment off the curve, an element not below r
     off = bytearray(raw[0])
     off[0] ^= 1
