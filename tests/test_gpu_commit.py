@@ -155,6 +155,41 @@ def test_library_verifies_the_full_size_opening(lib, ctx):
     assert lib.hyrax_verify(ctx, key, raw[1:] + raw[:1], point, t, rho_star, y)[0] == 2
 
 
+def test_full_size_weight_stack_rows_and_opening(lib, ctx):
+    """The weight stack of the 8 x 1024^2 window (2^23 int32, 4096 rows of 2048 columns; the key takes 12-bit
+    windows, 2.4 GB of tables): two rows recomputed by the oracle from the definition, all 4096 commitments the
+    same from a key with 8-bit windows, and the opening at a random point accepted by the library's verifier."""
+    import torch
+    from workloads import fcnn_window, CONFIG_SEED
+    say("hyrax_commit on the 2^23 weight stack")
+    wit = fcnn_window(CONFIG_SEED + 3, n_layers=8, width=1024, batch=64, steps=1)
+    vals = np.ascontiguousarray(wit["W"]).reshape(-1)
+    rows, cols = EC.matrix_shape(vals.size)
+    assert (rows, cols) == (4096, 2048)
+    rng = np.random.default_rng(13)
+    blind = [int.from_bytes(rng.bytes(31), "little") for _ in range(rows)]
+    x = lib.tensor_wrap_int(ctx, torch.from_numpy(vals).cuda())
+    key = lib.CommitKey(ctx, b"W", cols)
+    raw = lib.hyrax_commit(ctx, key, x, blind)
+    ctx.set_commit_window_bits(8)
+    try:
+        key8 = lib.CommitKey(ctx, b"W", cols)
+    finally:
+        ctx.set_commit_window_bits(0)
+    assert lib.hyrax_commit(ctx, key8, x, blind) == raw
+    key8.close()
+    say("  oracle: 2048 generators and two rows from the definition")
+    gens, h = EC.generators(b"W", cols)
+    for j in (0, rows - 3):
+        row = [int(v) for v in vals[j * cols:(j + 1) * cols]]
+        assert EC.point_to_bytes(EC.commit(row, blind[j], gens, h)) == raw[j]
+    point = [int.from_bytes(rng.bytes(31), "little") for _ in range(23)]
+    t, rho_star, y = lib.hyrax_open(ctx, x, blind, point)
+    assert lib.hyrax_verify(ctx, key, raw, point, t, rho_star, y)[0] == 0
+    assert lib.hyrax_verify(ctx, key, raw, point, t, rho_star, (y + 1) % R_MOD)[0] == 3
+    key.close()
+
+
 def test_claims_of_a_chained_window_open_against_the_commitments(lib, ctx):
     """Protocol zkdl end to end on one small window: the stacks A and W are committed, the chained window is
     proved, and the one claim it leaves on each of them is what the commitment opens to at the claim's point
