@@ -461,8 +461,11 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_pe_mid_i32(PeArgs p) {
 
 // Innermost axis contracted, int32 source: one wave per tile of 64 output rows and one chunk
 // of the axis.  The tile of integers is read row by row (each row segment is contiguous, so
-// the loads coalesce) and transposed through LDS; then lane = row, and beta_a is the same for
-// all lanes of an iteration.  Same column arithmetic as k_pe_mid_lazy<TK_I32>.
+// the loads coalesce; all 64 rows are requested before the first is used) and transposed through LDS; then
+// lane = row, and beta_a is the same for all lanes of an iteration.  Same arithmetic as
+// k_pe_mid_i32: ten signed 64-bit columns, nine multiply-adds per element, carried every fourth
+// element, the offset 2^56 2^261 at the end.
+constexpr int PE_INNER_ROWS = 64;   // rows of a tile requested together: the whole tile (16 KB in flight per wave)
 __global__ __launch_bounds__(64) void k_pe_inner_i32_lazy(PeArgs p) {
     __shared__ int32_t tile[64][65];
     __shared__ F9 sb[64];
@@ -472,39 +475,55 @@ __global__ __launch_bounds__(64) void k_pe_inner_i32_lazy(PeArgs p) {
     uint64_t a1 = a0 + p.a_chunk;
     if (a1 > p.A) a1 = p.A;
     const int32_t* src = (const int32_t*)p.src;
-    uint64_t cp[17], cn[17];
+    int64_t c[10];
 #pragma unroll
-    for (int k = 0; k < 17; ++k) cp[k] = cn[k] = 0;
-    int pending = 0;
-    const uint64_t rows_here = p.O - row0 < 64 ? p.O - row0 : 64;
+    for (int k = 0; k < 10; ++k) c[k] = 0;
+    const int rows_here = (int)(p.O - row0 < 64 ? p.O - row0 : 64);
     for (uint64_t at = a0; at < a1; at += 64) {
         const int na = (int)(a1 - at < 64 ? a1 - at : 64);
         if (lane < na) sb[lane] = fr_unpack(tab_ld(p.beta, at + lane));
-        for (uint64_t r = 0; r < rows_here; ++r)
-            if (lane < na) tile[r][lane] = src[(row0 + r) * p.A + at + lane];
+        const int32_t* seg = src + row0 * p.A + at + lane;
+        for (int r0 = 0; r0 < rows_here; r0 += PE_INNER_ROWS) {
+            int32_t x[PE_INNER_ROWS];
+#pragma unroll
+            for (int u = 0; u < PE_INNER_ROWS; ++u)
+                x[u] = (lane < na && r0 + u < rows_here) ? seg[(uint64_t)(r0 + u) * p.A] : 0;
+#pragma unroll
+            for (int u = 0; u < PE_INNER_ROWS; ++u) tile[r0 + u][lane] = x[u];
+        }
         __syncthreads();
-        if ((uint64_t)lane < rows_here) {
-            for (int k = 0; k < na; ++k) {
-                const int32_t x = tile[lane][k];
-                const F9 b9 = sb[k];
-                const uint32_t xp = x > 0 ? (uint32_t)x : 0u, xn = x < 0 ? (uint32_t)0 - (uint32_t)x : 0u;
-                f9_cols_mac_small(cp, b9, xp);
-                f9_cols_mac_small(cn, b9, xn);
-                if (++pending == 4) {
-                    pending = 0;
-                    f9_cols_norm<10>(cp);
-                    f9_cols_norm<10>(cn);
+        if (lane < rows_here) {
+            for (int k0 = 0; k0 < na; k0 += 4) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int k = k0 + u < na ? k0 + u : 0;
+                    const int64_t x = k0 + u < na ? (int64_t)tile[lane][k] : 0;
+                    const F9 b9 = sb[k];
+#pragma unroll
+                    for (int l = 0; l < 9; ++l) c[l] += (int64_t)(int32_t)b9.v[l] * x;
+                }
+                // four products below 2^60 in magnitude per column
+#pragma unroll
+                for (int l = 0; l + 1 < 10; ++l) {
+                    c[l + 1] += c[l] >> 29;
+                    c[l] &= (int64_t)frc::M29;
                 }
             }
         }
         __syncthreads();
     }
-    if ((uint64_t)lane < rows_here) {
-        f9_cols_norm<10>(cp);
-        f9_cols_norm<10>(cn);
+    if (lane < rows_here) {
+        // |sum| < 2^286 (chunks of at most 2^27 entries): with the offset the top column is positive
+        uint64_t cols[17];
+#pragma unroll
+        for (int k = 0; k < 17; ++k) cols[k] = k < 10 ? (uint64_t)c[k] : 0;
+        cols[9] += (uint64_t)1 << 56;
         const F9 r2 = fr_unpack(fr_const(frc::R2));
-        const F9 mp = f9_mul(f9_redc(cp), r2), mn = f9_mul(f9_redc(cn), r2);
-        tab_st(p.out, (uint64_t)blockIdx.y * p.O + row0 + lane, f9_to_fr(f9_sub(mp, mn)));
+        F9 off = f9_zero();
+        off.v[1] = 1u << 27;                                  // 2^56 as plain limbs
+        const F9 koff = f9_mul(off, r2);                      // 2^56 2^261 mod r (up to a multiple of r), below 2r
+        const F9 val = f9_mul(f9_redc(cols), r2);             // normal, below 2r
+        tab_st(p.out, (uint64_t)blockIdx.y * p.O + row0 + lane, f9_to_fr(f9_sub(val, koff)));
     }
 }
 
