@@ -571,6 +571,10 @@ int zkdl_selfbench(zkdl_ctx* ctx, int what, uint64_t work, double* units, double
 int zkdl_host_fr_mul(const zkdl_fr* a, const zkdl_fr* b, zkdl_fr* out);
 /* Re-derives the Montgomery constants by modular doubling; ZKDL_OK if they match. */
 int zkdl_selfcheck_constants(void);
+/* The split of a scalar that hyrax_verify hands to its kernels: k (32 bytes little-endian, any value) =
+ * a + b z^2 with z^2 = 0xd201000000010000^2 and a < z^2; out = a (16 bytes little-endian) then b (16 bytes).
+ * ZKDL_EINVAL if b does not fit 128 bits (k >= 2^128 z^2; never for k below r). */
+int zkdl_host_scalar_split(const zkdl_fr* k, uint8_t out[32]);
 
 #ifdef __cplusplus
 }

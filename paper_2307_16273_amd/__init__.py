@@ -10,12 +10,12 @@ from .binding import (Context, Transcript, FrTensor, ZkdlError, load_library, li
                       fr_tensor_upload, tensor_wrap_int, mle_partial_eval, sumcheck_product,
                       sumcheck_matmul, sumcheck_matmul_ft, sumcheck_matmul_general, sumcheck_hadamard, reindex_prove,
                       claims_merge_prove, zkrelu_prove, aggregate_prove, update_prove,
-                      host_fr_mul, selfcheck_constants, EXPORTED_SYMBOLS,
+                      host_fr_mul, host_scalar_split, selfcheck_constants, EXPORTED_SYMBOLS,
                       CommitKey, hyrax_commit, hyrax_open, hyrax_verify, commit_selfcheck, aggregate_verify)
 
 __all__ = ["Context", "Transcript", "FrTensor", "ZkdlError", "load_library", "library_path",
            "fr_tensor_upload", "tensor_wrap_int", "mle_partial_eval", "sumcheck_product",
            "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_matmul_general", "sumcheck_hadamard", "reindex_prove",
            "claims_merge_prove", "zkrelu_prove", "aggregate_prove", "update_prove",
-           "host_fr_mul", "selfcheck_constants", "EXPORTED_SYMBOLS",
+           "host_fr_mul", "host_scalar_split", "selfcheck_constants", "EXPORTED_SYMBOLS",
            "CommitKey", "hyrax_commit", "hyrax_open", "hyrax_verify", "commit_selfcheck", "aggregate_verify"]

@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = [
     "fr_tensor_upload", "zkdl_tensor_wrap_int", "zkdl_tensor_ndim", "zkdl_tensor_dim",
     "zkdl_tensor_numel", "zkdl_tensor_download", "zkdl_tensor_free",
     "mle_partial_eval", "sumcheck_product", "sumcheck_product_noalloc", "sumcheck_matmul", "sumcheck_matmul_ft", "sumcheck_matmul_general", "update_prove", "hyrax_verify", "sumcheck_hadamard",
-    "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "aggregate_prove_ft", "zkdl_host_fr_mul", "zkdl_selfcheck_constants",
+    "reindex_prove", "claims_merge_prove", "claims_merge_stack_prove", "zkrelu_prove", "zkrelu_prove_at", "aggregate_prove", "aggregate_prove_linked", "aggregate_prove_ft", "zkdl_host_fr_mul", "zkdl_selfcheck_constants", "zkdl_host_scalar_split",
     "zkdl_ctx_profile_enable", "zkdl_ctx_profile_reset", "zkdl_ctx_profile_read", "zkdl_selfbench",
     "zkdl_commit_key_create", "zkdl_commit_key_destroy", "zkdl_commit_key_generators", "hyrax_commit", "hyrax_open",
     "zkdl_commit_selfcheck", "aggregate_verify", "zkdl_host_aggregate_verify",
@@ -96,6 +96,7 @@ def load_library():
         "aggregate_prove_linked": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz, vp, psz],
         "aggregate_prove_ft": [vp, C.POINTER(FcnnWitness), vp, vp, psz, vp, psz],
         "zkdl_host_fr_mul": [vp, vp, vp], "zkdl_selfcheck_constants": [],
+        "zkdl_host_scalar_split": [vp, vp],
         "zkdl_ctx_profile_enable": [vp, i], "zkdl_ctx_profile_reset": [vp],
         "zkdl_ctx_profile_read": [vp, i, C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
         "zkdl_selfbench": [vp, i, u64, C.POINTER(C.c_double), C.POINTER(C.c_double)],
@@ -497,6 +498,14 @@ def host_fr_mul(a, b):
                                            C.create_string_buffer(int(b).to_bytes(32, "little"), 32), out),
            "zkdl_host_fr_mul")
     return int.from_bytes(out.raw, "little")
+
+
+def host_scalar_split(k):
+    """(a, b) with k = a + b z^2, a < z^2 (the split hyrax_verify uses), by the library's host code."""
+    out = C.create_string_buffer(32)
+    _check(load_library().zkdl_host_scalar_split(C.create_string_buffer(int(k).to_bytes(32, "little"), 32), out),
+           "zkdl_host_scalar_split")
+    return int.from_bytes(out.raw[:16], "little"), int.from_bytes(out.raw[16:], "little")
 
 
 def selfcheck_constants():

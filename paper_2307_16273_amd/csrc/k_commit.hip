@@ -655,6 +655,15 @@ static bool glv_split(const uint32_t k[8], uint32_t out[8]) {
     return c == 0;
 }
 
+extern "C" int zkdl_host_scalar_split(const zkdl_fr* k, uint8_t out[32]) {
+    if (!k || !out) return ZKDL_EINVAL;
+    uint32_t kw[8], ab[8];
+    memcpy(kw, k->le, 32);
+    if (!glv_split(kw, ab)) return ZKDL_EINVAL;
+    memcpy(out, ab, 32);
+    return ZKDL_OK;
+}
+
 // host-side check of the constants of fq.cuh (no GPU needed): Montgomery one and R^2 by repeated doubling,
 // the Montgomery factor, the square-root and inversion exponents
 static int commit_selfcheck_run() {

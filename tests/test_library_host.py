@@ -176,3 +176,22 @@ def test_host_verifier_on_general_form_proofs():
         assert got["verdict"] == 0, got["verdict"]
         assert got["points"] == ots.challenges and tr.digest() == ots.digest()
         _flip_everything(buf, 14, draws=n * d1 * d2 * d3 > 1)
+
+
+def test_host_scalar_split_is_the_division_by_z_squared():
+    """hyrax_verify multiplies by k as a P + b (-phi(P)) with k = a + b z^2: the host's long division against
+    Python's divmod, on the edge values of the quotient estimate and on random scalars."""
+    zz = 0xd201000000010000 ** 2
+    assert zz * zz - zz + 1 == R_MOD                              # r = z^4 - z^2 + 1
+    rng = np.random.default_rng(17)
+    ks = [0, 1, zz - 1, zz, zz + 1, R_MOD - 1, R_MOD, (1 << 128) * zz - 1, 3 * zz - 1, (zz - 1) * zz + zz - 1,
+          (1 << 255) - 1, (1 << 192) - 1, 1 << 160, ((1 << 128) - 1) * zz]
+    ks += [int.from_bytes(rng.bytes(32), "little") % R_MOD for _ in range(3000)]
+    ks += [(int.from_bytes(rng.bytes(16), "little") >> 1) * zz + d for d in (0, 1, zz - 1) for _ in range(200)]
+    ks += [int("".join(rng.choice(["00000000", "ffffffff"]) for _ in range(8)), 16) % ((1 << 128) * zz) for _ in range(500)]
+    for k in ks:
+        assert zk.host_scalar_split(k) == (k % zz, k // zz), hex(k)
+    with pytest.raises(zk.ZkdlError):
+        zk.host_scalar_split((1 << 128) * zz)                       # the quotient no longer fits 128 bits
+    with pytest.raises(zk.ZkdlError):
+        zk.host_scalar_split((1 << 256) - 1)
