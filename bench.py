@@ -287,8 +287,8 @@ def main():
                 coms = zk.hyrax_commit(ctx, key, xv)
                 op_med, _ = timed(lambda: zk.hyrax_open(ctx, xv, None, pt), 3)
                 t_row, _, y_val = zk.hyrax_open(ctx, xv, None, pt)
-                hv_med, _ = timed(lambda: zk.hyrax_verify(ctx, key, coms, pt, t_row, None, y_val), 3)
-                assert zk.hyrax_verify(ctx, key, coms, pt, t_row, None, y_val)[0] == 0
+                hv_med, _ = timed(lambda: zk.hyrax_verify(ctx, key, coms, pt, t_row, None, y_val, want_combined=False), 3)
+                assert zk.hyrax_verify(ctx, key, coms, pt, t_row, None, y_val, want_combined=False)[0] == 0
                 out["config"]["open_ms_A_stack_2p%d" % mm] = 1e3 * op_med
                 out["config"]["open_verify_ms_A_stack_2p%d" % mm] = 1e3 * hv_med
             key.close()

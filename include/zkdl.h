@@ -521,7 +521,8 @@ int hyrax_open(zkdl_ctx* ctx, const zkdl_tensor* X, const zkdl_fr* blind, const 
  * + log2 C canonical elements, row coordinates first; T: C elements; rho: rho* or NULL for zero blinding.
  * *verdict = 0 accepted, 1 malformed input (an element not below r, a commitment that is not an element of the
  * group of order r Sec. 2.3 works in: off the curve, or on it but outside the subgroup), 2 the opened row does not
- * match the combined commitment, 3 wrong evaluation.  combined_out (may be NULL): C* as 96 bytes.
+ * match the combined commitment, 3 wrong evaluation.  combined_out (may be NULL): C* as 96 bytes; without it the
+ * two sums are compared as projective points and no inversion is taken.
  * Both sums run on the GPU, eight lanes per term (every point operation shared by the eight; a scalar split in
  * two halves of 128 bits by the curve's endomorphism, 4-bit windows), next to the membership test of the
  * commitments; the weights, the split and the inner product on the host. */

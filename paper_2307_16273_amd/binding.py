@@ -566,9 +566,9 @@ def hyrax_open(ctx, x, blind, point):
     return _split_fr(t.raw, cols), int.from_bytes(rho.raw, "little"), int.from_bytes(y.raw, "little")
 
 
-def hyrax_verify(ctx, key, commitments, point, t, rho, y):
+def hyrax_verify(ctx, key, commitments, point, t, rho, y, want_combined=True):
     """commitments: list of 96-byte strings; t: the opened row; rho: rho* or None.  Returns (verdict, combined
-    commitment bytes); verdict 0 = accepted."""
+    commitment bytes, or None if not asked for); verdict 0 = accepted."""
     rows = len(commitments)
     cb = C.create_string_buffer(b"".join(commitments), 96 * rows)
     pb = C.create_string_buffer(_fr_bytes(point), max(32 * len(point), 1))
@@ -576,10 +576,10 @@ def hyrax_verify(ctx, key, commitments, point, t, rho, y):
     rb = C.create_string_buffer(_fr_bytes([rho]), 32) if rho is not None else None
     yb = C.create_string_buffer(_fr_bytes([y]), 32)
     verdict = C.c_int(-1)
-    comb = C.create_string_buffer(96)
+    comb = C.create_string_buffer(96) if want_combined else None
     _check(load_library().hyrax_verify(ctx.handle, key.handle, cb, rows, pb, len(point), tb, rb, yb, C.byref(verdict), comb),
            "hyrax_verify", ctx)
-    return verdict.value, comb.raw
+    return verdict.value, (comb.raw if want_combined else None)
 
 
 def commit_selfcheck():

@@ -499,9 +499,11 @@ __global__ __launch_bounds__(64) void k_msm_terms(const uint8_t* pts_bytes, uint
     if (threadIdx.x == 0) part[blockIdx.x] = acc;
 }
 
-// Block b: out + 96 b = affine bytes of the sum of part[first[b] .. first[b] + count[b]) (coordinates below 2q): one
-// wave, eight groups of lanes adding every eighth partial sum, three more additions, one inversion.
-__global__ __launch_bounds__(64) void k_msm_finish(const G1* part, uint64_t n0, uint64_t n1, uint8_t* out) {
+// Block b: the sum of part[first[b] .. first[b] + count[b]) (coordinates below 2q): one wave, eight groups of lanes
+// adding every eighth partial sum, three more additions; then either its affine bytes at out + 96 b (one inversion)
+// or, with proj != nullptr, the projective sum itself at proj[b], coordinates below q (the caller compares two sums
+// by cross-multiplication and needs no inversion).
+__global__ __launch_bounds__(64) void k_msm_finish(const G1* part, uint64_t n0, uint64_t n1, uint8_t* out, G1* proj) {
     const int j = threadIdx.x % COOP, grp = threadIdx.x / COOP;
     const G1* src = blockIdx.x ? part + n0 : part;
     const uint64_t n = blockIdx.x ? n1 : n0;
@@ -514,7 +516,10 @@ __global__ __launch_bounds__(64) void k_msm_finish(const G1* part, uint64_t n0, 
     }
 #pragma unroll 1
     for (int off = 32; off >= COOP; off >>= 1) acc = g1_coop<0>(acc, g1_shfl_down(acc, off), j);
-    if (threadIdx.x == 0) g1_to_bytes(g1_canonical(acc), out + 96 * blockIdx.x);
+    if (threadIdx.x == 0) {
+        if (proj) proj[blockIdx.x] = g1_canonical(acc);
+        else g1_to_bytes(g1_canonical(acc), out + 96 * blockIdx.x);
+    }
 }
 
 __global__ __launch_bounds__(64) void k_ck_export(const G1* gens, uint64_t first, uint64_t count, uint8_t* out) {
@@ -1002,9 +1007,12 @@ extern "C" int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uin
     uint32_t* d_scal = (uint32_t*)zk_alloc(ctx, scal.size() * 4);
     G1* d_part = (G1*)zk_alloc(ctx, sizeof(G1) * (g1 + g2));   // the blocks that check the subgroup write none
     G1* d_gens = (G1*)zk_alloc(ctx, sizeof(G1) * n2);   // G_0 .. G_{cols-1}, H
-    uint8_t* d_out = (uint8_t*)zk_alloc(ctx, 256);
+    uint8_t* d_out = (uint8_t*)zk_alloc(ctx, 256 + 2 * sizeof(G1));   // 2 x 96 bytes | the error flag's copy | 2 projective sums
+    G1* d_proj = d_out ? (G1*)(d_out + 256) : nullptr;
+    const bool affine = combined_out != nullptr;   // the bytes of C* are wanted: one inversion per sum
     int rc = (d_comm && d_scal && d_part && d_gens && d_out) ? ZKDL_OK : ZKDL_ENOMEM;
     uint8_t h_out[256];
+    G1 h_proj[2];
     hipError_t e = hipSuccess;
     if (rc == ZKDL_OK) {
         e = hipMemcpyAsync(d_comm, commitments, nrows * 96, hipMemcpyHostToDevice, ctx->stream);
@@ -1016,8 +1024,10 @@ extern "C" int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uin
         if (e == hipSuccess) {
             hipLaunchKernelGGL(k_msm_terms, dim3(g1 + g2 + g1), dim3(64), 0, ctx->stream, d_comm, (uint64_t)nrows, g1, d_gens,
                                n2, g2, d_scal, d_part, d_scal + 8 * (nrows + cols + 1), beta);
-            hipLaunchKernelGGL(k_msm_finish, dim3(2), dim3(64), 0, ctx->stream, d_part, (uint64_t)g1, (uint64_t)g2, d_out);
-            e = hipMemcpyAsync(h_out, d_out, 192, hipMemcpyDeviceToHost, ctx->stream);
+            hipLaunchKernelGGL(k_msm_finish, dim3(2), dim3(64), 0, ctx->stream, d_part, (uint64_t)g1, (uint64_t)g2, d_out,
+                               affine ? (G1*)nullptr : d_proj);
+            e = affine ? hipMemcpyAsync(h_out, d_out, 192, hipMemcpyDeviceToHost, ctx->stream)
+                       : hipMemcpyAsync(h_proj, d_proj, 2 * sizeof(G1), hipMemcpyDeviceToHost, ctx->stream);
             if (e == hipSuccess)
                 e = hipMemcpyAsync(h_out + 192, d_scal + 8 * (nrows + cols + 1), 4, hipMemcpyDeviceToHost, ctx->stream);
         }
@@ -1036,7 +1046,15 @@ extern "C" int hyrax_verify(zkdl_ctx* ctx, const zkdl_commit_key* key, const uin
     memcpy(&bad, h_out + 192, 4);
     if (bad) return ZKDL_OK;                       // verdict 1: a commitment is not an element of the group
     if (combined_out) memcpy(combined_out, h_out, 96);
-    if (memcmp(h_out, h_out + 96, 96) != 0) {
+    bool same;
+    if (affine) {
+        same = memcmp(h_out, h_out + 96, 96) == 0;
+    } else {   // X1 Z2 = X2 Z1 and Y1 Z2 = Y2 Z1 (the identity is (0, 1, 0): it equals only itself)
+        const G1 &a = h_proj[0], &b = h_proj[1];
+        same = fq_eq(fq_mul(a.X, b.Z), fq_mul(b.X, a.Z)) && fq_eq(fq_mul(a.Y, b.Z), fq_mul(b.Y, a.Z)) &&
+               fq_is_zero(a.Z) == fq_is_zero(b.Z);
+    }
+    if (!same) {
         *verdict = 2;                              // Commit(T; rho*) is not the combined commitment
         return ZKDL_OK;
     }

@@ -110,12 +110,15 @@ def test_library_verifies_openings_as_the_oracle_does(lib, ctx, numel, dtype, bl
     coms = [EC.point_from_bytes(c) for c in raw]
     assert comb == EC.point_to_bytes(_combined(coms, point, rows))
     assert verdict == 0
+    # without the bytes of C* the two sums are compared as projective points
+    assert lib.hyrax_verify(ctx, key, raw, point, t, rho_star if blinded else None, y, want_combined=False) == (0, None)
     gens, h = EC.generators(b"vfy", cols)
     assert EC.verify_opening(coms, point, t, rho_star if blinded else 0, y, gens, h)
     # tampering, with the oracle's verifier beside it
     def both(raw_, point_, t_, rho_, y_, want):
         v, _ = lib.hyrax_verify(ctx, key, raw_, point_, t_, rho_, y_)
         assert v == want
+        assert lib.hyrax_verify(ctx, key, raw_, point_, t_, rho_, y_, want_combined=False) == (want, None)
         with pytest.raises(AssertionError):
             EC.verify_opening([EC.point_from_bytes(c) for c in raw_], point_, t_, rho_ or 0, y_, gens, h)
     rho_in = rho_star if blinded else None
