@@ -108,7 +108,7 @@ int zkdl_last_hip_error(const zkdl_ctx* ctx);
  * depend on it.  1 <= threads <= 2^24, else ZKDL_EINVAL. */
 int zkdl_ctx_set_fill_threads(zkdl_ctx* ctx, uint64_t threads);
 /* Tuning: bits per window of the fixed-base tables that zkdl_commit_key_create builds for tensor entries from
- * now on: 8, 12, or 0 (the default) for 12 while a key's tables stay below 8 GiB and 8 otherwise.  Commitments
+ * now on: 8, 12, or 0 (the default) for 12 while a key's tables stay below 16 GiB and 8 otherwise.  Commitments
  * do not depend on it.  Another value: ZKDL_EINVAL. */
 int zkdl_ctx_set_commit_window_bits(zkdl_ctx* ctx, int bits);
 const char* zkdl_strerror(int err);
@@ -492,7 +492,7 @@ int zkdl_host_aggregate_verify(const uint8_t* proof, size_t proof_len, zkdl_tran
  * root y, multiplied by the cofactor (a candidate that becomes the identity is skipped); H is index
  * 0xFFFFFFFF.  ncols a power of two up to 2^15; max_bits 32 or 64: the widest tensor entry the key serves
  * (the tables hold the 2^w - 1 non-zero multiples per w-bit window and generator in affine form, 96 B each,
- * ceil(max_bits / w) windows: w = 12, 1.2 MB per generator at 32 bits, while that stays below 8 GiB for the
+ * ceil(max_bits / w) windows: w = 12, 1.2 MB per generator at 32 bits, while that stays below 16 GiB for the
  * key, else w = 8, 98 KB per generator; zkdl_ctx_set_commit_window_bits).
  * zkdl_commit_key_generators: generators first .. first + count - 1 (index ncols = H) as bytes, for checks. */
 typedef struct zkdl_commit_key zkdl_commit_key;

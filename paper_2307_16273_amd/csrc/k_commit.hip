@@ -12,7 +12,7 @@
 // signed integers, a negative entry x being the field element r - |x|, i.e. -|x| G.  The sum therefore
 // runs over fixed-base window tables: for every generator the multiples d 2^(wk) G, d = 1..2^w - 1, k < bits/w,
 // are built once with the key, in affine form (96 bytes an entry), and a commitment is a plain sum of one table
-// entry per non-zero w-bit digit of |x| - no doublings and no buckets.  w = 12 while the tables stay below 8 GiB
+// entry per non-zero w-bit digit of |x| - no doublings and no buckets.  w = 12 while the tables stay below 16 GiB
 // (1.2 MB per generator for 32-bit entries, 2.4 GB for 2048 columns: memory is what this GPU has), else w = 8.
 // The blinding term rho H (rho a full field element) uses the same kind of table with 32 windows.  All sums use the complete projective formulas of fq.cuh: a row's sum may be
 // taken in any order.
@@ -29,7 +29,7 @@ constexpr int CK_WBITS = 8;                      // bits per window of the blind
 constexpr int CK_DIGITS = (1 << CK_WBITS) - 1;   // its entries per window: d = 1..255
 constexpr int CK_H_WINDOWS = 256 / CK_WBITS;     // windows of a 255-bit blinding scalar
 constexpr int CK_WIDE_WBITS = 12;                // bits per window of a tensor entry when the tables fit CK_WIDE_MAX_BYTES
-constexpr uint64_t CK_WIDE_MAX_BYTES = (uint64_t)8 << 30;
+constexpr uint64_t CK_WIDE_MAX_BYTES = (uint64_t)16 << 30;   // up to 8192 columns of 32-bit entries (9.7 GB)
 constexpr int CK_MAX_LABEL = 16;
 
 struct LabelArg {
