@@ -350,42 +350,60 @@ __global__ __launch_bounds__(ZK_BLOCK) void k_pe_inner(PeArgs p) {
 
 // Lazy variants: the products of one output are summed as 64-bit columns of 29-bit limb
 // products and reduced once (f9_cols_*, f9_redc), instead of one Montgomery product and one
-// modular addition per source element.  Thread per output element (o, i); blockIdx.y selects
-// the chunk of the contracted axis; beta_a is the same for every thread of an iteration.
+// modular addition per source element.  Thread per output element (o, i), block = 256 consecutive
+// outputs; blockIdx.y selects the chunk of the contracted axis; beta_a is the same for every thread
+// of an iteration and is unpacked once per block into LDS.
 //
 // Fr source: sum_a beta_a T_a, 81 multiply-adds per element, both in Montgomery form, so the
 // reduced sum is the Montgomery form of the result.
 // (int32 sources: k_pe_mid_i32 and k_pe_inner_i32_lazy below; there x_a is a plain integer, nine
 // multiply-adds per element, and the sum is "beta times integer" already.)
+constexpr int PE_FR_TILE = 256;   // entries of beta unpacked into LDS at a time
 template <int KIND>
 __global__ __launch_bounds__(ZK_BLOCK) void k_pe_mid_lazy(PeArgs p) {
+    static_assert(KIND == TK_FR, "Fr sources only");
+    __shared__ uint32_t sb[9][PE_FR_TILE];
     const uint64_t n_out = p.O * p.I;
     const uint64_t a0 = (uint64_t)blockIdx.y * p.a_chunk;
     uint64_t a1 = a0 + p.a_chunk;
     if (a1 > p.A) a1 = p.A;
-    for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < n_out;
-         e += (uint64_t)gridDim.x * blockDim.x) {
-        const uint64_t o = e / p.I, i = e - o * p.I;
-        Fr res;
-        if (KIND == TK_FR) {
-            uint64_t c[17];
+    const uint64_t nblk = (n_out + ZK_BLOCK - 1) / ZK_BLOCK;
+    for (uint64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+        const uint64_t e = blk * ZK_BLOCK + threadIdx.x;
+        const bool live = e < n_out;
+        const uint64_t o = live ? e / p.I : 0, i = live ? e - o * p.I : 0;
+        uint64_t c[17];
 #pragma unroll
-            for (int k = 0; k < 17; ++k) c[k] = 0;
-            int pending = 0;
+        for (int k = 0; k < 17; ++k) c[k] = 0;
+        int pending = 0;
+        for (uint64_t at = a0; at < a1; at += PE_FR_TILE) {
+            const int na = (int)(a1 - at < PE_FR_TILE ? a1 - at : PE_FR_TILE);
+            __syncthreads();   // the previous tile is no longer read
+            if ((int)threadIdx.x < na) {   // beta of the tile, unpacked once per block (every thread reads the same entry)
+                const F9 b9 = fr_unpack(tab_ld(p.beta, at + threadIdx.x));
+#pragma unroll
+                for (int l = 0; l < 9; ++l) sb[l][threadIdx.x] = b9.v[l];
+            }
+            __syncthreads();
+            if (live) {
 #pragma unroll 2
-            for (uint64_t a = a0; a < a1; ++a) {
-                const F9 b9 = fr_unpack(tab_ld(p.beta, a));
-                const F9 x9 = fr_unpack(tab_ld(p.fr_src, (o * p.A + a) * p.I + i));
-                f9_cols_mac(c, b9, x9);
-                if (++pending == 4) {
-                    pending = 0;
-                    f9_cols_norm<17>(c);
+                for (int k = 0; k < na; ++k) {
+                    F9 b9;
+#pragma unroll
+                    for (int l = 0; l < 9; ++l) b9.v[l] = sb[l][k];
+                    const F9 x9 = fr_unpack(tab_ld(p.fr_src, (o * p.A + at + k) * p.I + i));
+                    f9_cols_mac(c, b9, x9);
+                    if (++pending == 4) {
+                        pending = 0;
+                        f9_cols_norm<17>(c);
+                    }
                 }
             }
-            f9_cols_norm<17>(c);
-            res = f9_to_fr(f9_norm_reduce(f9_redc(c)));
         }
-        tab_st(p.out, (uint64_t)blockIdx.y * n_out + e, res);
+        if (live) {
+            f9_cols_norm<17>(c);
+            tab_st(p.out, (uint64_t)blockIdx.y * n_out + e, f9_to_fr(f9_norm_reduce(f9_redc(c))));
+        }
     }
 }
 
