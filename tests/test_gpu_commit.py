@@ -158,6 +158,42 @@ def test_library_verifies_the_full_size_opening(lib, ctx):
     assert lib.hyrax_verify(ctx, key, raw[1:] + raw[:1], point, t, rho_star, y)[0] == 2
 
 
+@pytest.mark.parametrize("dtype,zeros", [("i32", 0.0), ("i32", 0.9), ("i32", 0.995), ("i64", 0.5), ("i64", 0.97)])
+def test_sparse_and_mixed_rows_agree_between_window_widths(lib, ctx, dtype, zeros):
+    """Rows whose entries have anything from one to 31 (63) bits and are mostly zero: few digits, rows whose digit
+    count is not a multiple of 64, empty rows.  Both window widths give the same commitments, and three rows
+    (the first, an all-zero one, the last) equal the oracle's sums."""
+    import torch
+    say(f"hyrax_commit sparse rows {dtype} zeros={zeros}")
+    rng = np.random.default_rng(int(zeros * 1000) + (7 if dtype == "i64" else 3))
+    numel = 1 << 14
+    top = 31 if dtype == "i32" else 63
+    bits = rng.integers(1, top + 1, numel)
+    vals = (rng.integers(0, 2 ** 62, numel, dtype=np.int64) >> (62 - bits)) * rng.choice([-1, 1], numel)
+    vals[rng.random(numel) < zeros] = 0
+    rows, cols = EC.matrix_shape(numel)
+    vals[5 * cols:6 * cols] = 0                                     # a row without any digit
+    vals = vals.astype(np.int32 if dtype == "i32" else np.int64)
+    x = lib.tensor_wrap_int(ctx, torch.from_numpy(vals).cuda())
+    blind = [int(v) for v in rng.integers(0, 2 ** 62, rows)]
+    blind[5] = 0                                                    # ... and no blinding: the identity
+    got = {}
+    for wbits in (8, 12):
+        ctx.set_commit_window_bits(wbits)
+        try:
+            key = lib.CommitKey(ctx, b"sparse", cols, 64 if dtype == "i64" else 32)
+        finally:
+            ctx.set_commit_window_bits(0)
+        got[wbits] = lib.hyrax_commit(ctx, key, x, blind)
+        key.close()
+    assert got[8] == got[12]
+    assert got[12][5] == bytes(96)
+    gens, h = EC.generators(b"sparse", cols)
+    for j in (0, 5, rows - 1):
+        row = [int(v) for v in vals[j * cols:(j + 1) * cols]]
+        assert EC.point_to_bytes(EC.commit(row, blind[j], gens, h)) == got[12][j]
+
+
 def test_full_size_weight_stack_rows_and_opening(lib, ctx):
     """The weight stack of the 8 x 1024^2 window (2^23 int32, 4096 rows of 2048 columns; the key takes 12-bit
     windows, 2.4 GB of tables): two rows recomputed by the oracle from the definition, all 4096 commitments the
