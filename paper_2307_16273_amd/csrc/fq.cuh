@@ -230,19 +230,11 @@ FQ_HD Fq fq_inv_euclid(const Fq& a) {
         U384 d;
         uint32_t bor = 0;
 #pragma unroll
-        for (int i = 0; i < W; ++i) {   // d = u - v modulo 2^384
-            const uint64_t x = (uint64_t)u.w[i] - v.w[i] - bor;
-            d.w[i] = (uint32_t)x;
-            bor = (uint32_t)(x >> 63);
-        }
+        for (int i = 0; i < W; ++i) d.w[i] = __builtin_subc(u.w[i], v.w[i], bor, &bor);   // d = u - v modulo 2^384
         const uint32_t sw = odd & (0u - bor);   // u odd and below v: the roles change
         uint32_t c = sw & 1u;
 #pragma unroll
-        for (int i = 0; i < W; ++i) {   // |u - v|
-            const uint64_t x = (uint64_t)(d.w[i] ^ sw) + c;
-            d.w[i] = (uint32_t)x;
-            c = (uint32_t)(x >> 32);
-        }
+        for (int i = 0; i < W; ++i) d.w[i] = __builtin_addc(d.w[i] ^ sw, 0u, c, &c);   // |u - v|
         c = 0;
         uint32_t any = 0;
 #pragma unroll
@@ -252,9 +244,7 @@ FQ_HD Fq fq_inv_euclid(const Fq& a) {
             any |= u.w[i];
             const uint32_t s_old = S.w[i], r_old = R.w[i];
             const uint32_t s_new = sw ? r_old : s_old, r_new = sw ? s_old : r_old;
-            const uint64_t x = (uint64_t)s_new + (r_new & odd) + c;   // S += R when u was odd
-            S.w[i] = (uint32_t)x;
-            c = (uint32_t)(x >> 32);
+            S.w[i] = __builtin_addc(s_new, r_new & odd, c, &c);   // S += R when u was odd
             R.w[i] = r_new;
         }
         flip ^= sw & 1u;
