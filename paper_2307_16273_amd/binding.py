@@ -320,25 +320,29 @@ def mle_partial_eval(ctx, t, axis_lo, axis_hi, point):
 
 
 class _Outputs:
-    def __init__(self, n_claims):
-        self.proof = C.create_string_buffer(PROOF_CAP)
+    """Output buffers of one call.  The two large ones belong to the context and are reused from call to call
+    (result() copies what the call wrote out of them before the next call can run)."""
+
+    def __init__(self, ctx, n_claims):
+        if getattr(ctx, "_out_bufs", None) is None:
+            ctx._out_bufs = (C.create_string_buffer(PROOF_CAP), C.create_string_buffer(32 * POINTS_CAP))
+        self.proof, self.points = ctx._out_bufs
         self.proof_len = C.c_size_t(PROOF_CAP)
         self.claims = C.create_string_buffer(32 * max(n_claims, 1))
-        self.points = C.create_string_buffer(32 * POINTS_CAP)
         self.npoints = C.c_size_t(POINTS_CAP)
         self.n_claims = n_claims
 
     def result(self):
-        return dict(proof=self.proof.raw[:self.proof_len.value],
+        return dict(proof=C.string_at(self.proof, self.proof_len.value),
                     claims=_split_fr(self.claims.raw, self.n_claims),
-                    points=_split_fr(self.points.raw, self.npoints.value))
+                    points=_split_fr(C.string_at(self.points, 32 * self.npoints.value), self.npoints.value))
 
 
 def sumcheck_product(ctx, tables, tr, noalloc=False):
     """noalloc: the entry point that allocates nothing (Fr tables of at most 2^18 entries)."""
     k = len(tables)
     arr = (C.c_void_p * k)(*[t.handle for t in tables])
-    o = _Outputs(k)
+    o = _Outputs(ctx, k)
     name = "sumcheck_product_noalloc" if noalloc else "sumcheck_product"
     _check(getattr(load_library(), name)(ctx.handle, arr, k, tr.handle, o.proof, C.byref(o.proof_len),
                                          o.claims, o.points, C.byref(o.npoints)), name, ctx)
@@ -346,7 +350,7 @@ def sumcheck_product(ctx, tables, tr, noalloc=False):
 
 
 def sumcheck_matmul(ctx, x0, x1, tr, transpose_x0=False, transpose_x1=False):
-    o = _Outputs(3)
+    o = _Outputs(ctx, 3)
     _check(load_library().sumcheck_matmul(ctx.handle, x0.handle, x1.handle, int(transpose_x0),
                                           int(transpose_x1), tr.handle, o.proof, C.byref(o.proof_len),
                                           o.claims, o.points, C.byref(o.npoints)), "sumcheck_matmul", ctx)
@@ -354,7 +358,7 @@ def sumcheck_matmul(ctx, x0, x1, tr, transpose_x0=False, transpose_x1=False):
 
 
 def sumcheck_matmul_ft(ctx, x0, x1, tr, transpose_x0=False, transpose_x1=False):
-    o = _Outputs(3)
+    o = _Outputs(ctx, 3)
     _check(load_library().sumcheck_matmul_ft(ctx.handle, x0.handle, x1.handle, int(transpose_x0),
                                              int(transpose_x1), tr.handle, o.proof, C.byref(o.proof_len),
                                              o.claims, o.points, C.byref(o.npoints)), "sumcheck_matmul_ft", ctx)
@@ -363,7 +367,7 @@ def sumcheck_matmul_ft(ctx, x0, x1, tr, transpose_x0=False, transpose_x1=False):
 
 def sumcheck_matmul_general(ctx, x0, x1, y, tr):
     """claims: Y~, X0~, X1~ at the final points (the general aggregated form takes Y as a stack)."""
-    o = _Outputs(3)
+    o = _Outputs(ctx, 3)
     _check(load_library().sumcheck_matmul_general(ctx.handle, x0.handle, x1.handle, y.handle, tr.handle, o.proof,
                                                   C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
            "sumcheck_matmul_general", ctx)
@@ -371,7 +375,7 @@ def sumcheck_matmul_general(ctx, x0, x1, y, tr):
 
 
 def sumcheck_hadamard(ctx, x0, x1, tr):
-    o = _Outputs(3)
+    o = _Outputs(ctx, 3)
     _check(load_library().sumcheck_hadamard(ctx.handle, x0.handle, x1.handle, tr.handle, o.proof,
                                             C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
            "sumcheck_hadamard", ctx)
@@ -388,7 +392,7 @@ def reindex_prove(ctx, x, maps, points, u, tr):
     pbufs = [C.create_string_buffer(_fr_bytes(p), max(32 * len(p), 1)) for p in points]
     pt_ptrs = (C.c_void_p * k)(*[C.addressof(b) for b in pbufs])
     ub = C.create_string_buffer(_fr_bytes(u), max(32 * len(u), 1))
-    o = _Outputs(k + 2)
+    o = _Outputs(ctx, k + 2)
     _check(load_library().reindex_prove(ctx.handle, x.handle, k, map_ptrs, lens, pt_ptrs, ub, tr.handle, o.proof,
                                         C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
            "reindex_prove", ctx)
@@ -403,7 +407,7 @@ def claims_merge_prove(ctx, x, points, tr, stack=False):
     name = "claims_merge_stack_prove" if stack else "claims_merge_prove"
     pbufs = [C.create_string_buffer(_fr_bytes(p), max(32 * len(p), 1)) for p in points]
     pt_ptrs = (C.c_void_p * k)(*[C.addressof(b) for b in pbufs])
-    o = _Outputs(k + 2)
+    o = _Outputs(ctx, k + 2)
     _check(getattr(load_library(), name)(ctx.handle, x.handle, k, pt_ptrs, tr.handle, o.proof,
                                          C.byref(o.proof_len), o.claims, o.points, C.byref(o.npoints)),
            name, ctx)
@@ -421,7 +425,7 @@ def zkrelu_prove(ctx, z, ga, tr, q=32, r=16, points=None):
     if ga is not None:
         gp, g_dev, gc, gk_ = _src_pointer(ga)
         assert gc == ZKDL_I64 and g_dev == z_dev
-    o = _Outputs(4)
+    o = _Outputs(ctx, 4)
     if points is not None:
         assert len(points) == 4
         flat = [x for pt in points for x in pt]
@@ -442,7 +446,7 @@ def update_prove(ctx, gw, tr, q=32, r=30):
     gp, g_dev, gc, keep = _src_pointer(gw)
     assert gc == ZKDL_I64
     d = int(np.prod(gw.shape))
-    o = _Outputs(0)
+    o = _Outputs(ctx, 0)
     claims = (Claim * 4)()
     nclaims = C.c_size_t(4)
     _check(load_library().update_prove(ctx.handle, gp, d, q, r, g_dev, tr.handle, o.proof, C.byref(o.proof_len),
@@ -471,7 +475,7 @@ def aggregate_prove(ctx, wit, tr, linked=False, ft=False):
     w = FcnnWitness(wit["L"], wit["B"], wit["width"], wit["T"], wit["Q"], wit["R"],
                     wit["A"].data_ptr(), wit["W"].data_ptr(), wit["GZ"].data_ptr(), wit["Zr"].data_ptr(),
                     wit["GA"].data_ptr())
-    o = _Outputs(0)
+    o = _Outputs(ctx, 0)
     if ft:
         assert not linked
         _check(load_library().aggregate_prove_ft(ctx.handle, C.byref(w), tr.handle, o.proof, C.byref(o.proof_len),
